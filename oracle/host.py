@@ -1,0 +1,184 @@
+"""ctypes binding of the C oracle; numpy arrays in, numpy arrays out.
+
+The arithmetic lives in ``kvtrim_oracle.c``; this file only marshals arguments.
+"""
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "kvtrim_oracle.c")
+_SO = os.path.join(_HERE, "libkvtrim_oracle.so")
+_lib = None
+
+
+def build(force=False):
+    """Compile the oracle with gcc (plain C, no contraction, OpenMP over segments in attend)."""
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off", "-fopenmp",
+               "-Wall", "-Wextra", "-o", _SO, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _SO
+
+
+class _CShape(C.Structure):
+    _fields_ = [("n_seq", C.c_int32), ("n_layers", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("n_q_heads", C.c_int32), ("head_dim", C.c_int32)]
+
+
+class _CCache(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("log_beta", C.c_void_p), ("pos", C.c_void_p),
+                ("seg_start", C.c_void_p), ("seg_len", C.c_void_p), ("cap", C.c_int64)]
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(_SO)
+        _lib.kvo_key_of_score.restype = C.c_uint32
+        _lib.kvo_key_of_score.argtypes = [C.c_float]
+        _lib.kvo_threads.restype = C.c_int
+        for name in ("kvo_select", "kvo_compact", "kvo_append"):
+            getattr(_lib, name).restype = C.c_int
+    return _lib
+
+
+@dataclass(frozen=True)
+class Shape:
+    n_seq: int
+    n_layers: int
+    n_kv_heads: int
+    n_q_heads: int
+    head_dim: int
+
+    @property
+    def nseg(self):
+        return self.n_seq * self.n_layers * self.n_kv_heads
+
+    @property
+    def group(self):
+        return self.n_q_heads // self.n_kv_heads
+
+    def c(self):
+        return _CShape(self.n_seq, self.n_layers, self.n_kv_heads, self.n_q_heads, self.head_dim)
+
+
+class HostCache:
+    """Ragged cache in host memory.  k, v hold bf16 bit patterns as uint16."""
+
+    def __init__(self, shape, cap):
+        self.shape = shape
+        self.cap = int(cap)
+        D = shape.head_dim
+        self.k = np.zeros((self.cap, D), np.uint16)
+        self.v = np.zeros((self.cap, D), np.uint16)
+        self.log_beta = np.zeros(self.cap, np.float32)
+        self.pos = np.zeros(self.cap, np.int32)
+        self.seg_start = np.zeros(shape.nseg, np.int64)
+        self.seg_len = np.zeros(shape.nseg, np.int32)
+
+    @classmethod
+    def from_arrays(cls, shape, k, v, log_beta, pos, seg_start, seg_len):
+        self = cls.__new__(cls)
+        self.shape = shape
+        self.cap = int(log_beta.shape[0])
+        self.k = np.ascontiguousarray(k, np.uint16).reshape(self.cap, shape.head_dim)
+        self.v = np.ascontiguousarray(v, np.uint16).reshape(self.cap, shape.head_dim)
+        self.log_beta = np.ascontiguousarray(log_beta, np.float32)
+        self.pos = np.ascontiguousarray(pos, np.int32)
+        self.seg_start = np.ascontiguousarray(seg_start, np.int64)
+        self.seg_len = np.ascontiguousarray(seg_len, np.int32)
+        return self
+
+    def c(self):
+        p = lambda a: a.ctypes.data_as(C.c_void_p)
+        return _CCache(p(self.k), p(self.v), p(self.log_beta), p(self.pos), p(self.seg_start),
+                       p(self.seg_len), self.cap)
+
+    def entry_index(self):
+        """Flat indices of every live entry, in (segment, position) order."""
+        return np.concatenate([np.arange(s, s + n, dtype=np.int64)
+                               for s, n in zip(self.seg_start, self.seg_len)] or [np.zeros(0, np.int64)])
+
+
+def _p(a):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def threads():
+    return int(lib().kvo_threads())
+
+
+def key_of_score(s):
+    return int(lib().kvo_key_of_score(C.c_float(float(s))))
+
+
+def score(cache, now):
+    now = np.ascontiguousarray(now, np.int32)
+    out = np.zeros(cache.cap, np.float32)
+    sh, cc = cache.shape.c(), cache.c()
+    lib().kvo_score(C.byref(sh), C.byref(cc), _p(now), _p(out))
+    return out
+
+
+def score_horizon(cache, now, horizon):
+    now = np.ascontiguousarray(now, np.int32)
+    out = np.zeros(cache.cap, np.float64)
+    sh, cc = cache.shape.c(), cache.c()
+    lib().kvo_score_horizon(C.byref(sh), C.byref(cc), _p(now), C.c_int32(int(horizon)), _p(out))
+    return out
+
+
+def select(cache, score_arr, budget):
+    score_arr = np.ascontiguousarray(score_arr, np.float32)
+    budget = np.ascontiguousarray(budget, np.int64)
+    assert budget.shape == (cache.shape.n_seq,)
+    keep = np.zeros(cache.cap, np.uint8)
+    kept = np.zeros(cache.shape.nseg, np.int32)
+    thr = np.zeros(cache.shape.n_seq, np.uint32)
+    sh, cc = cache.shape.c(), cache.c()
+    rc = lib().kvo_select(C.byref(sh), C.byref(cc), _p(score_arr), _p(budget), _p(keep), _p(kept), _p(thr))
+    if rc != 0:
+        raise MemoryError("oracle select: out of memory")
+    return keep, kept, thr
+
+
+def compact(src, keep, dst_cap, reserve):
+    keep = np.ascontiguousarray(keep, np.uint8)
+    dst = HostCache(src.shape, dst_cap)
+    sh, cs, cd = src.shape.c(), src.c(), dst.c()
+    rc = lib().kvo_compact(C.byref(sh), C.byref(cs), _p(keep), C.byref(cd), C.c_int32(int(reserve)))
+    if rc != 0:
+        raise OverflowError("oracle compact: destination capacity too small")
+    return dst
+
+
+def attend(cache, q, scale, layer_begin=0, layer_end=None, want_lse=True):
+    sh = cache.shape
+    if layer_end is None:
+        layer_end = sh.n_layers
+    q = np.ascontiguousarray(q, np.uint16).reshape(sh.n_seq, sh.n_layers, sh.n_q_heads, sh.head_dim)
+    out = np.zeros((sh.n_seq, sh.n_layers, sh.n_q_heads, sh.head_dim), np.float64)
+    lse = np.zeros((sh.n_seq, sh.n_layers, sh.n_q_heads), np.float64)
+    csh, cc = sh.c(), cache.c()
+    lib().kvo_attend(C.byref(csh), C.byref(cc), _p(q), C.c_int32(layer_begin), C.c_int32(layer_end),
+                     C.c_double(float(scale)), _p(out), _p(lse) if want_lse else None)
+    return out, lse
+
+
+def append(cache, k_new, v_new, log_beta_new, pos_new):
+    sh = cache.shape
+    log_beta_new = np.ascontiguousarray(log_beta_new, np.float32).reshape(sh.nseg, -1)
+    n_new = log_beta_new.shape[1]
+    k_new = np.ascontiguousarray(k_new, np.uint16).reshape(sh.nseg, n_new, sh.head_dim)
+    v_new = np.ascontiguousarray(v_new, np.uint16).reshape(sh.nseg, n_new, sh.head_dim)
+    pos_new = np.ascontiguousarray(pos_new, np.int32).reshape(sh.nseg, n_new)
+    csh, cc = sh.c(), cache.c()
+    rc = lib().kvo_append(C.byref(csh), C.byref(cc), _p(k_new), _p(v_new), _p(log_beta_new), _p(pos_new),
+                          C.c_int32(n_new))
+    if rc != 0:
+        raise OverflowError("oracle append: no room in a segment")

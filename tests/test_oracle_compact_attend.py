@@ -1,0 +1,202 @@
+"""Pins of the oracle's compaction and attention (CPU only).
+
+Compaction is checked against numpy boolean indexing (a library routine) and
+its invariants; attention against torch's CPU scaled_dot_product_attention in
+fp64, special cases with known answers, and the exact dilution identity of
+Cor. 3.2 evaluated with numpy.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import kvtrim_inputs as ki
+import oracle
+from helpers import bf16_bits, bits_to_f64, host_cache, live_mask
+
+
+def make(seg_len, S=1, L=2, H=2, G=2, D=64, reserve=1, salt=0):
+    w = ki.Workload("t", 0, S, L, H, G * H, D, (0,) * S, (0,) * S, 1, 3.0, 1.5)
+    c, now = ki.ragged_cache(w, seg_len, reserve=reserve, salt=salt)
+    return w, host_cache(w, c), now.numpy()
+
+
+def rand_q(w, seed):
+    g = torch.Generator().manual_seed(seed)
+    q = torch.randn(w.n_seq, w.n_layers, w.n_q_heads, w.head_dim, generator=g).to(torch.bfloat16)
+    return bf16_bits(q)
+
+
+# ----------------------------------------------------------------------------- compaction
+
+@pytest.mark.parametrize("seed", range(4))
+def test_compact_is_a_stable_filter_per_segment(seed):
+    rng = np.random.default_rng(seed)
+    seg_len = rng.integers(0, 60, 8)
+    w, hc, _ = make(seg_len, L=2, H=4, reserve=2, salt=seed)
+    keep = (rng.random(hc.cap) < 0.4).astype(np.uint8)
+    reserve = int(rng.integers(0, 4))
+    dst = oracle.compact(hc, keep, int(keep.sum()) + reserve * w.nseg + 5, reserve)
+    cursor = 0
+    for g in range(w.nseg):
+        s0, n = int(hc.seg_start[g]), int(hc.seg_len[g])
+        m = keep[s0:s0 + n].astype(bool)
+        assert dst.seg_start[g] == cursor and dst.seg_len[g] == m.sum()
+        d0 = cursor
+        np.testing.assert_array_equal(dst.k[d0:d0 + m.sum()], hc.k[s0:s0 + n][m])
+        np.testing.assert_array_equal(dst.v[d0:d0 + m.sum()], hc.v[s0:s0 + n][m])
+        np.testing.assert_array_equal(dst.log_beta[d0:d0 + m.sum()].view(np.uint32),
+                                      hc.log_beta[s0:s0 + n][m].view(np.uint32))
+        np.testing.assert_array_equal(dst.pos[d0:d0 + m.sum()], hc.pos[s0:s0 + n][m])
+        assert np.all(np.diff(dst.pos[d0:d0 + m.sum()]) > 0)
+        cursor += int(m.sum()) + reserve
+
+
+def test_compact_with_all_ones_is_identity_and_with_all_zeros_is_empty():
+    w, hc, _ = make([7, 0, 19, 4], reserve=1)
+    ones = np.ones(hc.cap, np.uint8)
+    dst = oracle.compact(hc, ones, hc.cap, 1)
+    np.testing.assert_array_equal(dst.seg_start, hc.seg_start)
+    np.testing.assert_array_equal(dst.seg_len, hc.seg_len)
+    live = live_mask(hc)
+    np.testing.assert_array_equal(dst.k[live], hc.k[live])
+    np.testing.assert_array_equal(dst.pos[live], hc.pos[live])
+    dst = oracle.compact(hc, np.zeros(hc.cap, np.uint8), 8, 2)
+    assert dst.seg_len.tolist() == [0, 0, 0, 0] and dst.seg_start.tolist() == [0, 2, 4, 6]
+
+
+def test_compact_reports_overflow_of_destination():
+    w, hc, _ = make([5, 5, 5, 5])
+    with pytest.raises(OverflowError):
+        oracle.compact(hc, np.ones(hc.cap, np.uint8), 23, 1)
+
+
+def test_append_writes_behind_segment_end_and_detects_full_segment():
+    w, hc, now = make([3, 0, 2, 1], reserve=1)
+    k_new = np.arange(w.nseg * 64, dtype=np.uint16).reshape(w.nseg, 64)
+    before_len = hc.seg_len.copy()
+    oracle.append(hc, k_new, k_new + 1, np.full(w.nseg, -0.5, np.float32), np.full(w.nseg, 99, np.int32))
+    np.testing.assert_array_equal(hc.seg_len, before_len + 1)
+    for g in range(w.nseg):
+        e = hc.seg_start[g] + hc.seg_len[g] - 1
+        np.testing.assert_array_equal(hc.k[e], k_new[g])
+        np.testing.assert_array_equal(hc.v[e], k_new[g] + 1)
+        assert hc.pos[e] == 99 and hc.log_beta[e] == np.float32(-0.5)
+    with pytest.raises(OverflowError):
+        oracle.append(hc, k_new, k_new, np.zeros(w.nseg, np.float32), np.full(w.nseg, 100, np.int32))
+
+
+# ----------------------------------------------------------------------------- attention
+
+def sdpa_reference(w, hc, qbits, scale):
+    """torch CPU SDPA in fp64, one call per segment."""
+    G, D = w.group, w.head_dim
+    out = np.zeros((w.n_seq, w.n_layers, w.n_q_heads, D))
+    lse = np.full((w.n_seq, w.n_layers, w.n_q_heads), -np.inf)
+    q = bits_to_f64(qbits).reshape(w.n_seq, w.n_layers, w.n_q_heads, D)
+    for s in range(w.n_seq):
+        for l in range(w.n_layers):
+            for h in range(w.n_kv_heads):
+                g = w.seg_id(s, l, h)
+                s0, n = int(hc.seg_start[g]), int(hc.seg_len[g])
+                if n == 0:
+                    continue
+                K = torch.from_numpy(bits_to_f64(hc.k[s0:s0 + n]))
+                V = torch.from_numpy(bits_to_f64(hc.v[s0:s0 + n]))
+                Q = torch.from_numpy(q[s, l, h * G:(h + 1) * G])
+                o = torch.nn.functional.scaled_dot_product_attention(Q[None], K[None], V[None], scale=scale)
+                out[s, l, h * G:(h + 1) * G] = o[0].numpy()
+                lse[s, l, h * G:(h + 1) * G] = torch.logsumexp(Q @ K.T * scale, dim=-1).numpy()
+    return out, lse
+
+
+@pytest.mark.parametrize("S,L,H,G,D", [(1, 2, 2, 2, 64), (2, 1, 2, 4, 128), (1, 1, 3, 7, 128)])
+def test_attend_equals_library_sdpa_in_fp64(S, L, H, G, D):
+    rng = np.random.default_rng(S * 100 + G)
+    seg_len = rng.integers(0, 70, S * L * H)
+    seg_len[0] = 0
+    w, hc, _ = make(seg_len, S, L, H, G, D, salt=G)
+    q = rand_q(w, 3)
+    scale = 1.0 / math.sqrt(D)
+    out, lse = oracle.attend(hc, q, scale)
+    ref, ref_lse = sdpa_reference(w, hc, q, scale)
+    np.testing.assert_allclose(out, ref, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(lse, ref_lse, rtol=1e-12)
+    assert np.all(out[0, 0, :G] == 0.0) and np.all(np.isneginf(lse[0, 0, :G]))     # empty segment
+
+
+def test_attend_single_entry_returns_its_value_row_exactly():
+    w, hc, _ = make([1, 1, 1, 1])
+    out, lse = oracle.attend(hc, rand_q(w, 1), 0.125)
+    for l in range(2):
+        for h in range(2):
+            e = int(hc.seg_start[w.seg_id(0, l, h)])
+            for j in range(2):
+                np.testing.assert_array_equal(out[0, l, h * 2 + j], bits_to_f64(hc.v[e]))
+
+
+def test_attend_uniform_keys_average_the_values_and_is_permutation_invariant():
+    w, hc, _ = make([16, 9, 0, 5])
+    s0 = int(hc.seg_start[0])
+    hc.k[s0:s0 + 16] = hc.k[s0]                         # identical keys -> uniform weights
+    q = rand_q(w, 2)
+    out, _ = oracle.attend(hc, q, 0.125)
+    np.testing.assert_allclose(out[0, 0, 0], bits_to_f64(hc.v[s0:s0 + 16]).mean(0), rtol=1e-13, atol=1e-14)
+    s1 = int(hc.seg_start[1])
+    perm = np.random.default_rng(0).permutation(9)
+    hc.k[s1:s1 + 9] = hc.k[s1:s1 + 9][perm]
+    hc.v[s1:s1 + 9] = hc.v[s1:s1 + 9][perm]
+    out2, _ = oracle.attend(hc, q, 0.125)
+    np.testing.assert_allclose(out2[0, 0, 2:4], out[0, 0, 2:4], rtol=1e-12, atol=1e-14)
+
+
+def test_layer_range_limits_what_is_written():
+    w, hc, _ = make([4, 4, 4, 4])
+    q = rand_q(w, 5)
+    full, _ = oracle.attend(hc, q, 0.125)
+    part, _ = oracle.attend(hc, q, 0.125, layer_begin=1, layer_end=2)
+    np.testing.assert_array_equal(part[0, 1], full[0, 1])
+    assert np.all(part[0, 0] == 0.0)
+
+
+def test_budget_covering_everything_gives_full_cache_attention():
+    # Sec. 2.1: with r = 1 everywhere Eq. reform is the full-cache attention.
+    w, hc, now = make([30, 12, 0, 21], salt=11)
+    q = rand_q(w, 7)
+    full, full_lse = oracle.attend(hc, q, 0.125)
+    keep, kept, _ = oracle.select(hc, oracle.score(hc, now), np.array([10 ** 6], np.int64))
+    dst = oracle.compact(hc, keep, hc.cap + 3, 1)
+    out, lse = oracle.attend(dst, q, 0.125)
+    np.testing.assert_array_equal(out, full)
+    np.testing.assert_array_equal(lse, full_lse)
+
+
+def test_hard_eviction_satisfies_the_dilution_identity():
+    # Cor. 3.2: delta^r = (rho_D/rho_U) delta / ((1 - delta) + (rho_D/rho_U) delta), exact for any
+    # retention weights; here r in {0,1} comes from score -> select -> compact, and the attention
+    # mass on the useful set U is read off the oracle's output by making V[:,0] the indicator of U.
+    n = 64
+    w, hc, now = make([n], L=1, H=1, G=2, salt=13)
+    rng = np.random.default_rng(5)
+    s0 = int(hc.seg_start[0])
+    useful = rng.random(n) < 0.25
+    one, zero = 0x3F80, 0x0000                      # bf16 bit patterns of 1.0 and 0.0
+    hc.v[s0:s0 + n, 0] = np.where(useful, one, zero)
+    q = rand_q(w, 17)
+    scale = 0.125
+    full, _ = oracle.attend(hc, q, scale)
+    keep, kept, _ = oracle.select(hc, oracle.score(hc, now), np.array([n // 2], np.int64))
+    r = keep[s0:s0 + n].astype(np.float64)
+    assert 0 < r[useful].sum() and 0 < r[~useful].sum() < (~useful).sum()
+    evicted, _ = oracle.attend(oracle.compact(hc, keep, n, 0), q, scale)
+    K = bits_to_f64(hc.k[s0:s0 + n])
+    for j in range(2):
+        z = K @ bits_to_f64(q.reshape(-1, 64)[j]) * scale
+        ez = np.exp(z - z.max())
+        rho_u = (r[useful] * ez[useful]).sum() / ez[useful].sum()
+        rho_d = (r[~useful] * ez[~useful]).sum() / ez[~useful].sum()
+        delta = 1.0 - full[0, 0, j, 0]
+        delta_r = 1.0 - evicted[0, 0, j, 0]
+        ratio = rho_d / rho_u
+        assert math.isclose(delta_r, ratio * delta / ((1 - delta) + ratio * delta), rel_tol=1e-10)
