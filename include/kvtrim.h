@@ -1,0 +1,156 @@
+/*
+ * kvtrim: decode-time hot path of global retention-based KV-cache eviction on
+ * one MI355X (gfx950).  C ABI; every data pointer is CALLER-OWNED DEVICE memory
+ * unless a comment says "host"; `hip_stream` is a hipStream_t passed as void*
+ * (NULL = the default stream).
+ *
+ * One decode / eviction step is
+ *     kvtrim_append  (support: the new token enters every segment)
+ *  -> kvtrim_score          stage 1
+ *  -> kvtrim_select_global  stage 2
+ *  -> kvtrim_compact        stage 3
+ *  -> kvtrim_decode_attn    stage 4
+ *
+ * Common rules
+ *  - Every call returns a kvtrim_status; nothing throws or aborts.  Host-visible
+ *    argument errors (null pointers, bad shapes, capacity larger than the context
+ *    was created for) return KVTRIM_EINVAL before anything is launched.
+ *  - The five step calls only enqueue kernels on `hip_stream`: no allocation, no
+ *    synchronisation, no host read-back, no memset nodes (a step can be captured
+ *    in a HIP graph).  Conditions only the device can see (a destination too
+ *    small, a `kept` array that disagrees with the mask) set a sticky device flag;
+ *    the kernel that finds the condition writes nothing out of bounds, and later
+ *    kernels of the same call return early.  kvtrim_poll_error reads and clears it.
+ *  - A context owns one workspace (allocated in kvtrim_create) that every call
+ *    reuses: calls on one context must be ordered on one stream.
+ *
+ * Ragged cache (kvtrim_cache)
+ *  A "segment" is the logical KV list of one (sequence, layer, KV head); segment
+ *  index g = (seq * n_layers + layer) * n_kv_heads + head; nseg = n_seq*n_layers*
+ *  n_kv_heads.  Segment g occupies entries [seg_start[g], seg_start[g]+seg_len[g])
+ *  of the flat arrays.  Segments are laid out in ascending g without overlap
+ *  (seg_start[g] + seg_len[g] <= seg_start[g+1]); free slots may follow a segment.
+ *  Inside a segment `pos` is strictly ascending.
+ *      k, v       bf16 [cap_entries][head_dim], row-major, 16-byte aligned base
+ *      log_beta   fp32 [cap_entries]   log of the retention coefficient, <= 0, not NaN
+ *      pos        int32 [cap_entries]  token position of the entry
+ *      seg_start  int64 [nseg]
+ *      seg_len    int32 [nseg]
+ *  Entries outside every segment are never read; what the calls leave in the
+ *  corresponding slots of their outputs is unspecified.
+ */
+#ifndef KVTRIM_H
+#define KVTRIM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct kvtrim_ctx kvtrim_ctx; /* opaque */
+
+typedef enum {
+    KVTRIM_OK = 0,
+    KVTRIM_EINVAL = -1, /* bad argument seen on the host */
+    KVTRIM_ENOMEM = -2, /* workspace allocation failed */
+    KVTRIM_EHIP = -3,   /* a HIP call failed; text in kvtrim_last_error */
+    KVTRIM_ECAP = -4,   /* device-side: destination / segment has no room */
+    KVTRIM_EMISMATCH = -5, /* device-side: `kept` does not match the mask */
+    KVTRIM_ELAYOUT = -6    /* device-side: segment table inconsistent with cap_entries */
+} kvtrim_status;
+
+typedef struct {
+    int32_t n_seq;      /* S >= 1 */
+    int32_t n_layers;   /* L >= 1 */
+    int32_t n_kv_heads; /* Hkv >= 1 */
+    int32_t n_q_heads;  /* Hq, a multiple of Hkv, Hq/Hkv <= 8 */
+    int32_t head_dim;   /* D: 64 or 128 */
+    int64_t max_entries; /* largest cap_entries of any cache passed to this context */
+} kvtrim_config;
+
+typedef struct {
+    void *k;
+    void *v;
+    float *log_beta;
+    int32_t *pos;
+    int64_t *seg_start;
+    int32_t *seg_len;
+    int64_t cap_entries;
+} kvtrim_cache;
+
+/* Context life cycle (host side, synchronous).  kvtrim_create allocates the
+ * workspace on the current device; kvtrim_workspace_bytes says how large it is. */
+kvtrim_status kvtrim_create(kvtrim_ctx **out, const kvtrim_config *cfg);
+kvtrim_status kvtrim_destroy(kvtrim_ctx *ctx);
+size_t kvtrim_workspace_bytes(const kvtrim_config *cfg);
+const char *kvtrim_last_error(const kvtrim_ctx *ctx); /* host string, owned by ctx */
+
+/* Outside the hot loop: waits for `hip_stream`, then returns and clears the
+ * sticky device flag (KVTRIM_OK, KVTRIM_ECAP, KVTRIM_EMISMATCH or KVTRIM_ELAYOUT). */
+kvtrim_status kvtrim_poll_error(kvtrim_ctx *ctx, void *hip_stream);
+
+/* Stage 1 - retention score, Sec. 4.2 Eq. (global_score) at lookahead T-t = 1,
+ * in log domain:  score[e] = float(now[seq] + 1 - pos[e]) * log_beta[e], exactly
+ * one IEEE binary32 multiply (round to nearest even).  now[seq] is the position of
+ * the newest token of the sequence (device int32 [n_seq]).
+ * score_out: device fp32 [cap_entries]; written for entries inside segments. */
+kvtrim_status kvtrim_score(kvtrim_ctx *ctx, const kvtrim_cache *c, const int32_t *now,
+                           float *score_out, void *hip_stream);
+
+/* Stage 2 - global eviction rule, Sec. 4.2: per sequence keep the
+ * min(budget[seq], count) entries that come first in the total order
+ *   (score descending by its IEEE bits mapped order-preservingly to uint32, so
+ *    -0 < +0; then layer ascending; head ascending; position ascending).
+ * No per-layer or per-head budget exists.  budget: device int64 [n_seq]
+ * (negative counts as 0).
+ * keep_out: device uint8 [cap_entries], 1 = retained, written for entries inside
+ * segments.  kept_out: device int32 [nseg], retained entries per segment.
+ * thr_key_out: optional (may be NULL) device uint32 [n_seq], key of the last
+ * retained entry in that order, 0xFFFFFFFF when nothing is retained. */
+kvtrim_status kvtrim_select_global(kvtrim_ctx *ctx, const kvtrim_cache *c, const float *score,
+                                   const int64_t *budget, uint8_t *keep_out, int32_t *kept_out,
+                                   uint32_t *thr_key_out, void *hip_stream);
+
+/* Stage 3 - variable-length per-(layer, head) caches, Sec. 4.2 "Implementation
+ * details", realised as a stable stream compaction: segment g of dst holds the
+ * entries of src segment g with keep[e] != 0 in their original order (K row, V
+ * row, log_beta, pos copied bit for bit), dst->seg_len[g] = kept[g] and
+ * dst->seg_start[g] = sum_{g' < g} (kept[g'] + reserve), i.e. `reserve` free slots
+ * follow every segment.  src and dst must not share buffers.  keep: device uint8
+ * [src->cap_entries]; kept: device int32 [nseg] as produced by stage 2.
+ * Device-side errors: KVTRIM_ECAP if sum(kept + reserve) > dst->cap_entries (then
+ * nothing is written), KVTRIM_EMISMATCH if kept[g] differs from the mask's count. */
+kvtrim_status kvtrim_compact(kvtrim_ctx *ctx, const kvtrim_cache *src, const uint8_t *keep,
+                             const int32_t *kept, kvtrim_cache *dst, int32_t reserve,
+                             void *hip_stream);
+
+/* Stage 4 - decode attention under hard eviction, Sec. 2.1 Eq. (reform) with
+ * r in {0,1}: for every segment of layers [layer_begin, layer_end) and each of its
+ * G = Hq/Hkv query heads hq = head*G + j,
+ *   z_i = (q . k_i) * softmax_scale, alpha = softmax(z), o = sum_i alpha_i v_i
+ * over the entries of the segment (bf16 inputs, fp32 accumulation).
+ * q: device bf16 [n_seq][n_layers][n_q_heads][head_dim].
+ * out: device fp32, same shape; lse: optional (may be NULL) device fp32
+ * [n_seq][n_layers][n_q_heads] = log sum_i exp(z_i).  An empty segment gives
+ * out = 0 and lse = -inf.  Heads of layers outside the range are not written. */
+kvtrim_status kvtrim_decode_attn(kvtrim_ctx *ctx, const kvtrim_cache *c, const void *q,
+                                 int32_t layer_begin, int32_t layer_end, float softmax_scale,
+                                 float *out, float *lse, void *hip_stream);
+
+/* Support - new tokens enter the cache (Sec. 3.2: beta is fixed when the token is
+ * first cached).  Appends n_new entries to every segment, in order, behind its
+ * current end and adds n_new to seg_len.  k_new, v_new: device bf16
+ * [nseg][n_new][head_dim]; log_beta_new: device fp32 [nseg][n_new]; pos_new: device
+ * int32 [nseg][n_new] (ascending, above the segment's last position).
+ * Device-side error KVTRIM_ECAP if some segment lacks n_new free slots before the
+ * next segment (or the end of the buffer); that segment is then left unchanged. */
+kvtrim_status kvtrim_append(kvtrim_ctx *ctx, kvtrim_cache *c, const void *k_new, const void *v_new,
+                            const float *log_beta_new, const int32_t *pos_new, int32_t n_new,
+                            void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVTRIM_H */

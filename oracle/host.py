@@ -70,12 +70,13 @@ class Shape:
 class HostCache:
     """Ragged cache in host memory.  k, v hold bf16 bit patterns as uint16."""
 
-    def __init__(self, shape, cap):
+    def __init__(self, shape, cap, with_rows=True):
         self.shape = shape
         self.cap = int(cap)
         D = shape.head_dim
-        self.k = np.zeros((self.cap, D), np.uint16)
-        self.v = np.zeros((self.cap, D), np.uint16)
+        rows = self.cap if with_rows else 0          # metadata-only caches serve score / select
+        self.k = np.zeros((rows, D), np.uint16)
+        self.v = np.zeros((rows, D), np.uint16)
         self.log_beta = np.zeros(self.cap, np.float32)
         self.pos = np.zeros(self.cap, np.int32)
         self.seg_start = np.zeros(shape.nseg, np.int64)
@@ -86,8 +87,8 @@ class HostCache:
         self = cls.__new__(cls)
         self.shape = shape
         self.cap = int(log_beta.shape[0])
-        self.k = np.ascontiguousarray(k, np.uint16).reshape(self.cap, shape.head_dim)
-        self.v = np.ascontiguousarray(v, np.uint16).reshape(self.cap, shape.head_dim)
+        self.k = np.ascontiguousarray(k, np.uint16).reshape(-1, shape.head_dim)
+        self.v = np.ascontiguousarray(v, np.uint16).reshape(-1, shape.head_dim)
         self.log_beta = np.ascontiguousarray(log_beta, np.float32)
         self.pos = np.ascontiguousarray(pos, np.int32)
         self.seg_start = np.ascontiguousarray(seg_start, np.int64)

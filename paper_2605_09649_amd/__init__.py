@@ -1,0 +1,14 @@
+"""kvtrim: MI355X-native decode-time hot path of global retention-based KV eviction.
+
+The work happens in libkvtrim.so (hand-written HIP for gfx950, C ABI declared in
+include/kvtrim.h).  This package is the thin ctypes binding: same names as the
+C entry points, argument marshalling only.  Importing it never loads the library;
+the first call does, and fails loudly if it has not been built.
+"""
+from .binding import (Cache, Context, KvtrimError, kvtrim_append, kvtrim_compact, kvtrim_decode_attn,
+                      kvtrim_poll_error, kvtrim_score, kvtrim_select_global, kvtrim_workspace_bytes,
+                      library_path, load_library)
+
+__all__ = ["Cache", "Context", "KvtrimError", "kvtrim_append", "kvtrim_compact", "kvtrim_decode_attn",
+           "kvtrim_poll_error", "kvtrim_score", "kvtrim_select_global", "kvtrim_workspace_bytes",
+           "library_path", "load_library"]

@@ -1,0 +1,190 @@
+"""ctypes binding of libkvtrim.so.  PyTorch tensors only provide device memory and the stream."""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libkvtrim.so")
+_lib = None
+
+STATUS = {0: "KVTRIM_OK", -1: "KVTRIM_EINVAL", -2: "KVTRIM_ENOMEM", -3: "KVTRIM_EHIP", -4: "KVTRIM_ECAP",
+          -5: "KVTRIM_EMISMATCH", -6: "KVTRIM_ELAYOUT"}
+
+EXPORTS = ["kvtrim_create", "kvtrim_destroy", "kvtrim_workspace_bytes", "kvtrim_last_error",
+           "kvtrim_poll_error", "kvtrim_score", "kvtrim_select_global", "kvtrim_compact",
+           "kvtrim_decode_attn", "kvtrim_append"]
+
+
+class KvtrimError(RuntimeError):
+    def __init__(self, status, text=""):
+        self.status = status
+        super().__init__(f"{STATUS.get(status, status)} {text}".strip())
+
+
+class _Config(C.Structure):
+    _fields_ = [("n_seq", C.c_int32), ("n_layers", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("n_q_heads", C.c_int32), ("head_dim", C.c_int32), ("max_entries", C.c_int64)]
+
+
+class _Cache(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("log_beta", C.c_void_p), ("pos", C.c_void_p),
+                ("seg_start", C.c_void_p), ("seg_len", C.c_void_p), ("cap_entries", C.c_int64)]
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads libkvtrim.so; raises if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        lib = C.CDLL(_LIB_PATH)
+        lib.kvtrim_create.argtypes = [C.POINTER(C.c_void_p), C.POINTER(_Config)]
+        lib.kvtrim_destroy.argtypes = [C.c_void_p]
+        lib.kvtrim_workspace_bytes.argtypes = [C.POINTER(_Config)]
+        lib.kvtrim_workspace_bytes.restype = C.c_size_t
+        lib.kvtrim_last_error.argtypes = [C.c_void_p]
+        lib.kvtrim_last_error.restype = C.c_char_p
+        lib.kvtrim_poll_error.argtypes = [C.c_void_p, C.c_void_p]
+        lib.kvtrim_score.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.kvtrim_select_global.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.c_void_p,
+                                             C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.kvtrim_compact.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.POINTER(_Cache),
+                                       C.c_int32, C.c_void_p]
+        lib.kvtrim_decode_attn.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_int32, C.c_int32,
+                                           C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.kvtrim_append.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.c_int32, C.c_void_p]
+        for name in EXPORTS:
+            if name not in ("kvtrim_workspace_bytes", "kvtrim_last_error"):
+                getattr(lib, name).restype = C.c_int
+        _lib = lib
+    return _lib
+
+
+def _config(n_seq, n_layers, n_kv_heads, n_q_heads, head_dim, max_entries):
+    return _Config(n_seq, n_layers, n_kv_heads, n_q_heads, head_dim, max_entries)
+
+
+def kvtrim_workspace_bytes(n_seq, n_layers, n_kv_heads, n_q_heads, head_dim, max_entries):
+    cfg = _config(n_seq, n_layers, n_kv_heads, n_q_heads, head_dim, max_entries)
+    return int(load_library().kvtrim_workspace_bytes(C.byref(cfg)))
+
+
+def _ptr(t, dtype=None):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensor required"
+    if dtype is not None:
+        assert t.dtype == dtype, (t.dtype, dtype)
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+class Cache:
+    """Ragged cache: device tensors plus the C view of them."""
+
+    def __init__(self, k, v, log_beta, pos, seg_start, seg_len):
+        self.k, self.v, self.log_beta, self.pos, self.seg_start, self.seg_len = k, v, log_beta, pos, seg_start, seg_len
+        self.cap = int(log_beta.shape[0])
+        self.c = _Cache(_ptr(k, torch.bfloat16).value, _ptr(v, torch.bfloat16).value,
+                        _ptr(log_beta, torch.float32).value, _ptr(pos, torch.int32).value,
+                        _ptr(seg_start, torch.int64).value, _ptr(seg_len, torch.int32).value, self.cap)
+
+    @classmethod
+    def from_dict(cls, d, device="cuda"):
+        t = {n: d[n].to(device) for n in ("k", "v", "log_beta", "pos", "seg_start", "seg_len")}
+        return cls(**t)
+
+    @classmethod
+    def empty(cls, nseg, head_dim, cap, device="cuda"):
+        return cls(torch.zeros(cap, head_dim, dtype=torch.bfloat16, device=device),
+                   torch.zeros(cap, head_dim, dtype=torch.bfloat16, device=device),
+                   torch.zeros(cap, dtype=torch.float32, device=device),
+                   torch.zeros(cap, dtype=torch.int32, device=device),
+                   torch.zeros(nseg, dtype=torch.int64, device=device),
+                   torch.zeros(nseg, dtype=torch.int32, device=device))
+
+
+class Context:
+    """Owns a kvtrim_ctx (the library's workspace on the current device)."""
+
+    def __init__(self, n_seq, n_layers, n_kv_heads, n_q_heads, head_dim, max_entries):
+        lib = load_library()
+        if not torch.cuda.is_available():
+            raise RuntimeError("kvtrim needs a GPU: there is no CPU fallback")
+        torch.cuda.init()
+        self.shape = (n_seq, n_layers, n_kv_heads, n_q_heads, head_dim)
+        self.nseg = n_seq * n_layers * n_kv_heads
+        self.max_entries = int(max_entries)
+        cfg = _config(n_seq, n_layers, n_kv_heads, n_q_heads, head_dim, max_entries)
+        h = C.c_void_p()
+        rc = lib.kvtrim_create(C.byref(h), C.byref(cfg))
+        if rc != 0:
+            raise KvtrimError(rc, "kvtrim_create")
+        self.handle = h
+
+    def close(self):
+        if getattr(self, "handle", None):
+            load_library().kvtrim_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def last_error(self):
+        return load_library().kvtrim_last_error(self.handle).decode()
+
+
+def _check(ctx, rc, what):
+    if rc != 0:
+        raise KvtrimError(rc, f"{what}: {ctx.last_error()}")
+
+
+def kvtrim_poll_error(ctx, stream=None):
+    """Synchronises the stream; returns the status code of the sticky device flag (0 = OK)."""
+    return int(load_library().kvtrim_poll_error(ctx.handle, _stream(stream)))
+
+
+def kvtrim_score(ctx, cache, now, score_out, stream=None):
+    _check(ctx, load_library().kvtrim_score(ctx.handle, C.byref(cache.c), _ptr(now, torch.int32),
+                                            _ptr(score_out, torch.float32), _stream(stream)), "kvtrim_score")
+
+
+def kvtrim_select_global(ctx, cache, score, budget, keep_out, kept_out, thr_key_out=None, stream=None):
+    _check(ctx, load_library().kvtrim_select_global(
+        ctx.handle, C.byref(cache.c), _ptr(score, torch.float32), _ptr(budget, torch.int64),
+        _ptr(keep_out, torch.uint8), _ptr(kept_out, torch.int32), _ptr(thr_key_out), _stream(stream)),
+        "kvtrim_select_global")
+
+
+def kvtrim_compact(ctx, src, keep, kept, dst, reserve, stream=None):
+    _check(ctx, load_library().kvtrim_compact(ctx.handle, C.byref(src.c), _ptr(keep, torch.uint8),
+                                              _ptr(kept, torch.int32), C.byref(dst.c), int(reserve),
+                                              _stream(stream)), "kvtrim_compact")
+
+
+def kvtrim_decode_attn(ctx, cache, q, layer_begin, layer_end, softmax_scale, out, lse=None, stream=None):
+    _check(ctx, load_library().kvtrim_decode_attn(ctx.handle, C.byref(cache.c), _ptr(q, torch.bfloat16),
+                                                  int(layer_begin), int(layer_end), float(softmax_scale),
+                                                  _ptr(out, torch.float32), _ptr(lse, torch.float32),
+                                                  _stream(stream)), "kvtrim_decode_attn")
+
+
+def kvtrim_append(ctx, cache, k_new, v_new, log_beta_new, pos_new, n_new, stream=None):
+    _check(ctx, load_library().kvtrim_append(ctx.handle, C.byref(cache.c), _ptr(k_new, torch.bfloat16),
+                                             _ptr(v_new, torch.bfloat16), _ptr(log_beta_new, torch.float32),
+                                             _ptr(pos_new, torch.int32), int(n_new), _stream(stream)),
+           "kvtrim_append")

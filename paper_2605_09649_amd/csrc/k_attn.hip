@@ -1,0 +1,307 @@
+// Stage 4: GQA decode attention over the ragged retained caches (Sec. 2.1, Eq. reform, r in {0,1}).
+//
+// Split-K over fixed-size chunks of each segment so that very unequal segment lengths still
+// fill the chip.  Inside a chunk a wavefront walks tiles of 16 rows:
+//   Q.K^T  one MFMA 16x16 accumulator per tile (rows = 16 keys, columns = the G query heads,
+//          padded to 16); K fragments are loaded straight from HBM in the operand layout
+//          (lane = key row, four lanes share 64 contiguous bytes of the row).
+//   P.V    vector FMAs: a lane owns one 16-byte column slice of the row, so V is read fully
+//          coalesced (16 lanes = one 256-byte row) and the probability of (query, row) is
+//          fetched from its accumulator lane with a DPP row broadcast.
+// Each 16-lane row group of a wavefront is an independent online-softmax stream (rows
+// 4b..4b+3 of every tile); at the end of the chunk the four streams of a wavefront are merged
+// with lane shuffles, the four wavefronts through LDS, and the chunks of a segment by
+// k_att_combine.  Logits are kept in base-2 units.
+#include "kvtrim_device.h"
+
+namespace kvtrim {
+
+constexpr int ATT_THREADS = 256;
+
+typedef __attribute__((ext_vector_type(4))) float float4v;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) short short4v;
+
+__global__ __launch_bounds__(1024) void k_att_plan(CacheView c, Shape sh, Workspace ws, int chunk,
+                                                   int layer_begin, int layer_end, int64_t max_chunks) {
+    __shared__ int64_t lds64[17];
+    const int H = sh.n_kv_heads, L = sh.n_layers;
+    auto in_range = [=](int g) {
+        const int layer = (g / H) % L;
+        return layer >= layer_begin && layer < layer_end;
+    };
+    build_chunk_table(c.seg_len, c.seg_start, sh.nseg, in_range, chunk, c.cap, ws.att_chunk_prefix,
+                      ws.att_chunk_seg, max_chunks, ws.err, lds64);
+}
+
+// broadcast lane `Q` of every 16-lane row to the whole row
+template <int Q>
+__device__ __forceinline__ float row_bcast(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x150 + Q, 0xF, 0xF, false));
+}
+
+template <int D>
+struct Frag;
+template <>
+struct Frag<128> {
+    typedef uint4 vec;                       // 8 bf16
+    static constexpr int E = 8;
+    static __device__ __forceinline__ float4v mma(vec a, vec b, float4v c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ void unpack(vec x, float* f) {
+        f[0] = __uint_as_float(x.x << 16); f[1] = __uint_as_float(x.x & 0xffff0000u);
+        f[2] = __uint_as_float(x.y << 16); f[3] = __uint_as_float(x.y & 0xffff0000u);
+        f[4] = __uint_as_float(x.z << 16); f[5] = __uint_as_float(x.z & 0xffff0000u);
+        f[6] = __uint_as_float(x.w << 16); f[7] = __uint_as_float(x.w & 0xffff0000u);
+    }
+    static __device__ __forceinline__ vec zero() { return make_uint4(0, 0, 0, 0); }
+};
+template <>
+struct Frag<64> {
+    typedef uint2 vec;                       // 4 bf16
+    static constexpr int E = 4;
+    static __device__ __forceinline__ float4v mma(vec a, vec b, float4v c) {
+        return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(short4v, a), __builtin_bit_cast(short4v, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ void unpack(vec x, float* f) {
+        f[0] = __uint_as_float(x.x << 16); f[1] = __uint_as_float(x.x & 0xffff0000u);
+        f[2] = __uint_as_float(x.y << 16); f[3] = __uint_as_float(x.y & 0xffff0000u);
+    }
+    static __device__ __forceinline__ vec zero() { return make_uint2(0, 0); }
+};
+
+template <int G, int E, int QI>
+struct PV {   // o[QI..G) += bcast(p, q) * v
+    static __device__ __forceinline__ void run(float (&o)[G][E], float p, const float* vf) {
+        const float pb = row_bcast<QI>(p);
+#pragma unroll
+        for (int e = 0; e < E; ++e) o[QI][e] = fmaf(pb, vf[e], o[QI][e]);
+        PV<G, E, QI + 1>::run(o, p, vf);
+    }
+    static __device__ __forceinline__ void scale(float (&o)[G][E], float a) {
+        const float ab = row_bcast<QI>(a);
+#pragma unroll
+        for (int e = 0; e < E; ++e) o[QI][e] *= ab;
+        PV<G, E, QI + 1>::scale(o, a);
+    }
+};
+template <int G, int E>
+struct PV<G, E, G> {
+    static __device__ __forceinline__ void run(float (&)[G][E], float, const float*) {}
+    static __device__ __forceinline__ void scale(float (&)[G][E], float) {}
+};
+
+// partial layout: [chunk][G][D + 2] = (m in base-2 units, l, o[D] unnormalised)
+template <int D, int G>
+__global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const uint16_t* __restrict__ q,
+                                                             Shape sh, Workspace ws, int chunk,
+                                                             float scale_log2) {
+    typedef Frag<D> F;
+    typedef typename F::vec vec;
+    constexpr int E = F::E;
+    constexpr int NSTREAM = ATT_THREADS / 64;
+    __shared__ float s_m[NSTREAM][G], s_l[NSTREAM][G];
+    __shared__ float s_o[NSTREAM][G][D];
+
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    const int total = ws.att_chunk_prefix[sh.nseg];
+    const int ch = blockIdx.x;
+    if (ch >= total) return;
+    const int seg = ws.att_chunk_seg[ch];
+    const int off = (ch - ws.att_chunk_prefix[seg]) * chunk;
+    const int len = c.seg_len[seg];
+    const int row_end = min(len, off + chunk);                    // rows [off, row_end) of the segment
+    const int64_t base = c.seg_start[seg];
+    const int c16 = lane & 15, b4 = lane >> 4;
+
+    // query fragments: lane (query c16, k-group b4), MFMA step j covers elements (4j + b4)*E ..
+    const int seq = seg / sh.segs_per_seq, lh = seg % sh.segs_per_seq;
+    const int layer = lh / sh.n_kv_heads, head = lh % sh.n_kv_heads;
+    const int64_t qrow = ((int64_t)seq * sh.n_layers + layer) * sh.n_q_heads + (int64_t)head * G + c16;
+    vec qf[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        qf[j] = c16 < G ? reinterpret_cast<const vec*>(q + qrow * D)[4 * j + b4] : F::zero();
+
+    float o[G][E];
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int e = 0; e < E; ++e) o[g][e] = 0.f;
+    float m = -INFINITY, l = 0.f;
+
+    const vec* kp = reinterpret_cast<const vec*>(c.k);
+    const vec* vp = reinterpret_cast<const vec*>(c.v);
+    constexpr int VPR = D / E;                                    // vectors per row = 16
+
+    for (int r0 = off + wave * 16; r0 < row_end; r0 += 64) {
+        const int last = row_end - 1;
+        // K in MFMA operand layout: lane -> row r0 + c16, vectors 4j + b4
+        const int64_t krow = base + min(r0 + c16, last);
+        vec kf[4], vf[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) kf[j] = kp[krow * VPR + 4 * j + b4];
+        // V coalesced: lane -> row r0 + 4*b4 + i, vector c16
+#pragma unroll
+        for (int i = 0; i < 4; ++i) vf[i] = vp[(base + min(r0 + 4 * b4 + i, last)) * VPR + c16];
+
+        float4v acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc = F::mma(kf[j], qf[j], acc);
+        // acc[i] = q(c16) . k(r0 + 4*b4 + i)
+        float z[4];
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            z[i] = (r0 + 4 * b4 + i < row_end) ? acc[i] * scale_log2 : -INFINITY;
+            tmax = fmaxf(tmax, z[i]);
+        }
+        const float m_new = fmaxf(m, tmax);
+        const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m - m_safe);   // m = -inf gives 0; l and o are 0 then
+        float p[4];
+        float psum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            p[i] = __builtin_amdgcn_exp2f(z[i] - m_safe);
+            psum += p[i];
+        }
+        l = l * alpha + psum;
+        m = m_new;
+        if (__any(alpha != 1.0f)) PV<G, E, 0>::scale(o, alpha);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float vfl[E];
+            F::unpack(vf[i], vfl);
+            PV<G, E, 0>::run(o, p[i], vfl);
+        }
+    }
+
+    // merge the four row-group streams of the wavefront (lanes xor 16, xor 32), then the four
+    // wavefronts of the block through LDS
+    float m_all = fmaxf(m, __shfl_xor(m, 16, 64));
+    m_all = fmaxf(m_all, __shfl_xor(m_all, 32, 64));
+    const float m_fin = m_all == -INFINITY ? 0.f : m_all;
+    const float wgt = __builtin_amdgcn_exp2f(m - m_fin);          // 0 for a stream that saw no row
+    float l_all = l * wgt;
+    l_all += __shfl_xor(l_all, 16, 64);
+    l_all += __shfl_xor(l_all, 32, 64);
+    PV<G, E, 0>::scale(o, wgt);
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            float x = o[g][e];
+            x += __shfl_xor(x, 16, 64);
+            x += __shfl_xor(x, 32, 64);
+            o[g][e] = x;
+        }
+    if (b4 == 0) {
+        if (c16 < G) {
+            s_m[wave][c16] = m_all;
+            s_l[wave][c16] = l_all;
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int e = 0; e < E; ++e) s_o[wave][g][c16 * E + e] = o[g][e];
+    }
+    __syncthreads();
+    float* part = ws.att_partial + (size_t)ch * G * (D + 2);
+    for (int idx = tid; idx < G * D; idx += ATT_THREADS) {
+        const int g = idx / D, d = idx % D;
+        float M = -INFINITY;
+#pragma unroll
+        for (int s = 0; s < NSTREAM; ++s) M = fmaxf(M, s_m[s][g]);
+        const float Ms = M == -INFINITY ? 0.f : M;
+        float accd = 0.f, lsum = 0.f;
+#pragma unroll
+        for (int s = 0; s < NSTREAM; ++s) {
+            const float w = __builtin_amdgcn_exp2f(s_m[s][g] - Ms);
+            accd += s_o[s][g][d] * w;
+            lsum += s_l[s][g] * w;
+        }
+        part[g * (D + 2) + 2 + d] = accd;
+        if (d == 0) {
+            part[g * (D + 2)] = M;
+            part[g * (D + 2) + 1] = lsum;
+        }
+    }
+}
+
+// One block per segment of the layer range: merges the partial results of its chunks.
+template <int D>
+__global__ __launch_bounds__(ATT_THREADS) void k_att_combine(Shape sh, Workspace ws, int layer_begin,
+                                                             int layer_end, float* __restrict__ out,
+                                                             float* __restrict__ lse) {
+    const int G = sh.group;
+    const int nl = layer_end - layer_begin;
+    const int per = nl * sh.n_kv_heads;
+    const int seq = blockIdx.x / per, r = blockIdx.x % per;
+    const int layer = layer_begin + r / sh.n_kv_heads, head = r % sh.n_kv_heads;
+    const int seg = (seq * sh.n_layers + layer) * sh.n_kv_heads + head;
+    const int c0 = ws.att_chunk_prefix[seg], c1 = ws.att_chunk_prefix[seg + 1];
+    const int64_t hq0 = ((int64_t)seq * sh.n_layers + layer) * sh.n_q_heads + (int64_t)head * G;
+    const float LN2 = 0.6931471805599453f;
+    for (int idx = threadIdx.x; idx < G * D; idx += ATT_THREADS) {
+        const int g = idx / D, d = idx % D;
+        float M = -INFINITY;
+        for (int cc = c0; cc < c1; ++cc) M = fmaxf(M, ws.att_partial[((size_t)cc * G + g) * (D + 2)]);
+        const float Ms = M == -INFINITY ? 0.f : M;
+        float acc = 0.f, lsum = 0.f;
+        for (int cc = c0; cc < c1; ++cc) {
+            const float* p = ws.att_partial + ((size_t)cc * G + g) * (D + 2);
+            const float w = __builtin_amdgcn_exp2f(p[0] - Ms);
+            acc += p[2 + d] * w;
+            lsum += p[1] * w;
+        }
+        out[(hq0 + g) * D + d] = lsum > 0.f ? acc / lsum : 0.f;
+        if (d == 0 && lse) lse[hq0 + g] = lsum > 0.f ? (M + __builtin_amdgcn_logf(lsum)) * LN2 : -INFINITY;
+    }
+}
+
+template <int D, int G>
+static void launch_partial(const CacheView& c, const uint16_t* q, const Shape& sh, const Workspace& ws,
+                           int chunk, float scale_log2, unsigned blocks, hipStream_t st) {
+    hipLaunchKernelGGL((k_att_partial<D, G>), dim3(blocks), dim3(ATT_THREADS), 0, st, c, q, sh, ws, chunk, scale_log2);
+}
+
+template <int D>
+static bool dispatch_partial(int G, const CacheView& c, const uint16_t* q, const Shape& sh, const Workspace& ws,
+                             int chunk, float scale_log2, unsigned blocks, hipStream_t st) {
+    switch (G) {
+#define KVTRIM_CASE(g) case g: launch_partial<D, g>(c, q, sh, ws, chunk, scale_log2, blocks, st); return true;
+        KVTRIM_CASE(1) KVTRIM_CASE(2) KVTRIM_CASE(3) KVTRIM_CASE(4) KVTRIM_CASE(5) KVTRIM_CASE(6) KVTRIM_CASE(7) KVTRIM_CASE(8)
+#undef KVTRIM_CASE
+        default: return false;
+    }
+}
+
+int att_chunk_for(const kvtrim_ctx*, int64_t cap) {
+    int64_t chunk = (cap / 16384 + 63) / 64 * 64;
+    return (int)(chunk < 256 ? 256 : chunk);
+}
+
+kvtrim_status launch_attn(kvtrim_ctx* ctx, const CacheView& c, const uint16_t* q, int32_t layer_begin,
+                          int32_t layer_end, float scale, float* out, float* lse, hipStream_t st) {
+    const Shape& sh = ctx->shape;
+    const Workspace& ws = ctx->ws;
+    const int chunk = att_chunk_for(ctx, c.cap);
+    const int64_t max_chunks = c.cap / chunk + sh.nseg;
+    const float scale_log2 = scale * 1.4426950408889634f;
+    hipLaunchKernelGGL(k_att_plan, dim3(1), dim3(1024), 0, st, c, sh, ws, chunk, layer_begin, layer_end, max_chunks);
+    bool ok = sh.head_dim == 128
+                  ? dispatch_partial<128>(sh.group, c, q, sh, ws, chunk, scale_log2, (unsigned)max_chunks, st)
+                  : dispatch_partial<64>(sh.group, c, q, sh, ws, chunk, scale_log2, (unsigned)max_chunks, st);
+    if (!ok) return KVTRIM_EINVAL;
+    const unsigned nblk = (unsigned)(sh.n_seq * (layer_end - layer_begin) * sh.n_kv_heads);
+    if (sh.head_dim == 128)
+        hipLaunchKernelGGL(k_att_combine<128>, dim3(nblk), dim3(ATT_THREADS), 0, st, sh, ws, layer_begin, layer_end, out, lse);
+    else
+        hipLaunchKernelGGL(k_att_combine<64>, dim3(nblk), dim3(ATT_THREADS), 0, st, sh, ws, layer_begin, layer_end, out, lse);
+    KVTRIM_HIP(ctx, hipGetLastError());
+    return KVTRIM_OK;
+}
+
+}  // namespace kvtrim

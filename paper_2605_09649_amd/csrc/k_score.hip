@@ -1,0 +1,74 @@
+// Stage 1 (retention score in log domain) and the append support kernel.
+#include "kvtrim_device.h"
+
+namespace kvtrim {
+
+// Sec. 4.2, Eq. (global_score) at lookahead 1: log G~ = (now + 1 - pos) * log(beta), one fp32
+// multiply.  `bps` blocks share a segment and stride over its entries.
+__global__ __launch_bounds__(256) void k_score(CacheView c, const int32_t* __restrict__ now,
+                                               float* __restrict__ score, int segs_per_seq, int bps) {
+    const int seg = blockIdx.x / bps, part = blockIdx.x % bps;
+    const int len = c.seg_len[seg];
+    const int64_t start = c.seg_start[seg];
+    if (len < 0 || start < 0 || start + len > c.cap) return;     // never index outside the buffers
+    const int t1 = now[seg / segs_per_seq] + 1;
+    const float* lb = c.log_beta + start;
+    const int32_t* pos = c.pos + start;
+    float* out = score + start;
+    for (int j = part * 256 + threadIdx.x; j < len; j += bps * 256)
+        out[j] = __fmul_rn((float)(t1 - pos[j]), lb[j]);
+}
+
+kvtrim_status launch_score(kvtrim_ctx* ctx, const CacheView& c, const int32_t* now, float* score,
+                           hipStream_t st) {
+    const Shape& sh = ctx->shape;
+    int64_t bps = c.cap / ((int64_t)sh.nseg * 1024);
+    bps = bps < 1 ? 1 : (bps > 64 ? 64 : bps);
+    hipLaunchKernelGGL(k_score, dim3((unsigned)(sh.nseg * bps)), dim3(256), 0, st, c, now, score,
+                       sh.segs_per_seq, (int)bps);
+    KVTRIM_HIP(ctx, hipGetLastError());
+    return KVTRIM_OK;
+}
+
+// One block per segment: copies the n_new rows behind the segment's end (16 bytes per lane)
+// and the per-entry metadata, then bumps seg_len.  A segment without room is left alone.
+__global__ __launch_bounds__(256) void k_append(CacheViewMut c, const uint16_t* __restrict__ k_new,
+                                                const uint16_t* __restrict__ v_new,
+                                                const float* __restrict__ lb_new,
+                                                const int32_t* __restrict__ pos_new, int n_new, int nseg,
+                                                int head_dim, int32_t* err) {
+    const int seg = blockIdx.x;
+    const int len = c.seg_len[seg];
+    const int64_t start = c.seg_start[seg];
+    const int64_t limit = (seg + 1 < nseg) ? c.seg_start[seg + 1] : c.cap;
+    if (len < 0 || start < 0 || limit > c.cap || start + len + n_new > limit) {
+        if (threadIdx.x == 0) atomicOr(err, ERR_CAP);
+        return;
+    }
+    const int vec_per_row = head_dim / 8;                         // uint4 (8 bf16) per row
+    const uint4* ks = reinterpret_cast<const uint4*>(k_new) + (int64_t)seg * n_new * vec_per_row;
+    const uint4* vs = reinterpret_cast<const uint4*>(v_new) + (int64_t)seg * n_new * vec_per_row;
+    uint4* kd = reinterpret_cast<uint4*>(c.k) + (start + len) * vec_per_row;
+    uint4* vd = reinterpret_cast<uint4*>(c.v) + (start + len) * vec_per_row;
+    for (int i = threadIdx.x; i < n_new * vec_per_row; i += blockDim.x) {
+        kd[i] = ks[i];
+        vd[i] = vs[i];
+    }
+    for (int i = threadIdx.x; i < n_new; i += blockDim.x) {
+        c.log_beta[start + len + i] = lb_new[(int64_t)seg * n_new + i];
+        c.pos[start + len + i] = pos_new[(int64_t)seg * n_new + i];
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) c.seg_len[seg] = len + n_new;
+}
+
+kvtrim_status launch_append(kvtrim_ctx* ctx, const CacheViewMut& c, const uint16_t* k_new, const uint16_t* v_new,
+                            const float* lb_new, const int32_t* pos_new, int32_t n_new, hipStream_t st) {
+    const Shape& sh = ctx->shape;
+    hipLaunchKernelGGL(k_append, dim3(sh.nseg), dim3(256), 0, st, c, k_new, v_new, lb_new, pos_new, n_new,
+                       sh.nseg, sh.head_dim, ctx->ws.err);
+    KVTRIM_HIP(ctx, hipGetLastError());
+    return KVTRIM_OK;
+}
+
+}  // namespace kvtrim

@@ -1,0 +1,292 @@
+// Stage 2: one global top-B selection per sequence (Sec. 4.2, eviction rule).
+//
+// Exact selection by a three-pass most-significant-digit radix select (11 + 11 + 10 bits)
+// on the order-preserving uint32 image of the fp32 score.  Each pass builds per-block
+// histograms in LDS, merges them with device-scope atomics, and the last block to finish
+// walks the merged histogram from the top to fix the next digits of the threshold key.
+// Entries above the threshold are kept; entries equal to it are kept in storage order
+// (segment ascending, position ascending = layer, head, position) until the budget is
+// met, which needs an ordered count of ties per chunk and an exclusive scan over chunks.
+#include "kvtrim_device.h"
+
+namespace kvtrim {
+
+constexpr int SEL_THREADS = 256;
+constexpr int CNT_THREADS = 1024;
+
+__global__ __launch_bounds__(1024) void k_sel_plan(CacheView c, Shape sh, const int64_t* __restrict__ budget,
+                                                   Workspace ws, int32_t* __restrict__ kept_out) {
+    __shared__ int64_t lds64[17];
+    build_chunk_table(c.seg_len, c.seg_start, sh.nseg, [](int) { return true; }, SEL_CHUNK, c.cap, ws.sel_chunk_prefix,
+                      ws.sel_chunk_seg, ws.max_sel_chunks, ws.err, lds64);
+    for (int i = threadIdx.x; i < 3 * sh.n_seq * RADIX_BINS; i += blockDim.x) ws.hist[i] = 0;
+    for (int i = threadIdx.x; i < 8; i += blockDim.x) ws.done[i] = 0;
+    for (int g = threadIdx.x; g < sh.nseg; g += blockDim.x) kept_out[g] = 0;
+    const bool empty = ws.sel_chunk_prefix[sh.nseg] == 0;   // also the state after a layout error
+    for (int seq = 0; seq < sh.n_seq; ++seq) {
+        int64_t n = 0;
+        if (!empty)
+            for (int g = threadIdx.x; g < sh.segs_per_seq; g += blockDim.x) n += c.seg_len[seq * sh.segs_per_seq + g];
+        n = block_sum<int64_t>(n, lds64);
+        if (threadIdx.x == 0) {
+            int64_t b = budget[seq];
+            if (b < 0) b = 0;
+            SelState st;
+            st.prefix = 0;
+            st.thr_key = 0xFFFFFFFFu;
+            st.count = n;
+            st.want = b < n ? b : n;
+            st.rank = st.want;
+            st.tie_quota = 0;
+            st.keep_none = st.want == 0;
+            st.pad = 0;
+            ws.sel[seq] = st;
+        }
+    }
+}
+
+template <int PASS>
+__device__ __forceinline__ bool digit_of(uint32_t key, uint32_t prefix, int* bin) {
+    if (PASS == 0) {
+        *bin = key >> 21;
+        return true;
+    } else if (PASS == 1) {
+        *bin = (key >> 10) & 2047;
+        return (key >> 21) == prefix;
+    } else {
+        *bin = key & 1023;
+        return (key >> 10) == prefix;
+    }
+}
+
+// Histogram of the next digit over the entries whose higher digits equal the prefix found so
+// far.  Blocks take contiguous ranges of chunks; the LDS histogram is flushed when the
+// sequence changes and at the end.
+template <int PASS>
+__global__ __launch_bounds__(SEL_THREADS) void k_sel_hist(CacheView c, const float* __restrict__ score,
+                                                          Shape sh, Workspace ws,
+                                                          uint32_t* __restrict__ thr_out) {
+    constexpr int NB = PASS == 2 ? 1024 : 2048;
+    __shared__ uint32_t h[NB];
+    __shared__ int64_t lds64[17];
+    __shared__ int is_last;
+    const int tid = threadIdx.x;
+    const int total = ws.sel_chunk_prefix[sh.nseg];
+    const int cpb = (total + gridDim.x - 1) / gridDim.x;
+    const int c0 = min(total, (int)blockIdx.x * cpb), c1 = min(total, c0 + cpb);
+    uint32_t* hist = ws.hist + (size_t)PASS * sh.n_seq * RADIX_BINS;
+
+    for (int i = tid; i < NB; i += SEL_THREADS) h[i] = 0;
+    __syncthreads();
+    int cur_seq = -1;
+    uint32_t prefix = 0;
+    bool skip = false;
+    for (int ch = c0; ch < c1; ++ch) {
+        const int seg = ws.sel_chunk_seg[ch];
+        const int seq = seg / sh.segs_per_seq;
+        if (seq != cur_seq) {
+            if (cur_seq >= 0) {
+                __syncthreads();
+                for (int i = tid; i < NB; i += SEL_THREADS) {
+                    uint32_t v = h[i];
+                    if (v) atomicAdd(&hist[(size_t)cur_seq * RADIX_BINS + i], v);
+                    h[i] = 0;
+                }
+                __syncthreads();
+            }
+            cur_seq = seq;
+            prefix = ws.sel[seq].prefix;
+            skip = ws.sel[seq].keep_none != 0;
+        }
+        if (skip) continue;
+        const int off = (ch - ws.sel_chunk_prefix[seg]) * SEL_CHUNK;
+        const int end = min(c.seg_len[seg], off + SEL_CHUNK);
+        const float* s = score + c.seg_start[seg];
+        for (int j = off + tid; j < end; j += SEL_THREADS) {
+            int bin;
+            if (digit_of<PASS>(key_of_score(s[j]), prefix, &bin)) atomicAdd(&h[bin], 1u);
+        }
+    }
+    __syncthreads();
+    if (cur_seq >= 0) {
+        for (int i = tid; i < NB; i += SEL_THREADS) {
+            uint32_t v = h[i];
+            if (v) atomicAdd(&hist[(size_t)cur_seq * RADIX_BINS + i], v);
+        }
+    }
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) is_last = atomicAdd(&ws.done[PASS], 1u) == gridDim.x - 1;
+    __syncthreads();
+    if (!is_last) return;
+    __threadfence();
+
+    // Last block: per sequence, walk the histogram from the top bin down to the bin that
+    // holds the entry of rank `rank` (1-based, in descending key order).
+    constexpr int PER = NB / SEL_THREADS;   // bins per thread, thread 0 owns the highest bins
+    for (int seq = 0; seq < sh.n_seq; ++seq) {
+        SelState st = ws.sel[seq];
+        if (st.keep_none) {
+            if (PASS == 2 && tid == 0 && thr_out) thr_out[seq] = 0xFFFFFFFFu;
+            continue;
+        }
+        const uint32_t* hs = hist + (size_t)seq * RADIX_BINS;
+        uint32_t cnt[PER];
+        int64_t mine = 0;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            cnt[i] = __hip_atomic_load(&hs[NB - 1 - (tid * PER + i)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            mine += cnt[i];
+        }
+        int64_t tot;
+        int64_t above = block_excl_scan<int64_t>(mine, lds64, &tot);
+        if (above < st.rank && st.rank <= above + mine) {
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                if (st.rank <= above + cnt[i]) {
+                    const uint32_t bin = NB - 1 - (tid * PER + i);
+                    const int bits = PASS == 2 ? RADIX_BITS2 : (PASS == 1 ? RADIX_BITS1 : RADIX_BITS0);
+                    st.prefix = (st.prefix << bits) | bin;
+                    st.rank -= above;
+                    if (PASS == 2) {
+                        st.thr_key = st.prefix;
+                        st.tie_quota = st.rank;
+                        if (thr_out) thr_out[seq] = st.thr_key;
+                    }
+                    ws.sel[seq] = st;
+                    break;
+                }
+                above += cnt[i];
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// Per chunk: entries above the threshold (added to the segment's kept count) and entries
+// equal to it.  The last block then turns the per-chunk tie counts into exclusive prefixes
+// per sequence and credits the ties that fit into the quota to their segments.
+__global__ __launch_bounds__(CNT_THREADS) void k_sel_count(CacheView c, const float* __restrict__ score,
+                                                           Shape sh, Workspace ws,
+                                                           int32_t* __restrict__ kept_out) {
+    __shared__ int64_t lds64[17];
+    __shared__ int32_t lds32[17];
+    __shared__ int is_last;
+    const int tid = threadIdx.x;
+    const int total = ws.sel_chunk_prefix[sh.nseg];
+    const int ch = blockIdx.x;
+    if (ch < total) {
+        const int seg = ws.sel_chunk_seg[ch];
+        const SelState st = ws.sel[seg / sh.segs_per_seq];
+        int gt = 0, eq = 0;
+        if (!st.keep_none) {
+            const int off = (ch - ws.sel_chunk_prefix[seg]) * SEL_CHUNK;
+            const int end = min(c.seg_len[seg], off + SEL_CHUNK);
+            const float* s = score + c.seg_start[seg];
+            for (int j = off + tid; j < end; j += CNT_THREADS) {
+                const uint32_t key = key_of_score(s[j]);
+                gt += key > st.thr_key;
+                eq += key == st.thr_key;
+            }
+        }
+        gt = block_sum<int32_t>(gt, lds32);
+        eq = block_sum<int32_t>(eq, lds32);
+        if (tid == 0) {
+            if (gt) atomicAdd(&kept_out[seg], gt);
+            ws.chunk_eq[ch] = eq;
+        }
+    }
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) is_last = atomicAdd(&ws.done[3], 1u) == gridDim.x - 1;
+    __syncthreads();
+    if (!is_last) return;
+    __threadfence();
+
+    for (int seq = 0; seq < sh.n_seq; ++seq) {
+        const int cb = ws.sel_chunk_prefix[seq * sh.segs_per_seq];
+        const int ce = ws.sel_chunk_prefix[(seq + 1) * sh.segs_per_seq];
+        const int64_t quota = ws.sel[seq].tie_quota;
+        int64_t running = 0;
+        for (int base = cb; base < ce; base += CNT_THREADS) {
+            const int cc = base + tid;
+            int64_t v = cc < ce ? (int64_t)__hip_atomic_load(&ws.chunk_eq[cc], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+            int64_t tot;
+            int64_t ex = block_excl_scan<int64_t>(v, lds64, &tot);
+            if (cc < ce) {
+                const int64_t tb = running + ex;
+                ws.chunk_tie_base[cc] = tb;
+                if (v > 0 && tb < quota) {
+                    const int64_t take = min(v, quota - tb);
+                    atomicAdd(&kept_out[ws.sel_chunk_seg[cc]], (int32_t)take);
+                }
+            }
+            running += tot;
+        }
+    }
+}
+
+// keep[e] = key > thr, or key == thr and the entry is among the first `quota` ties of its
+// sequence in storage order.
+__global__ __launch_bounds__(SEL_THREADS) void k_sel_mask(CacheView c, const float* __restrict__ score,
+                                                          Shape sh, Workspace ws, uint8_t* __restrict__ keep) {
+    __shared__ int32_t lds32[17];
+    const int tid = threadIdx.x;
+    const int total = ws.sel_chunk_prefix[sh.nseg];
+    const int ch = blockIdx.x;
+    if (ch >= total) return;
+    const int seg = ws.sel_chunk_seg[ch];
+    const SelState st = ws.sel[seg / sh.segs_per_seq];
+    const int off = (ch - ws.sel_chunk_prefix[seg]) * SEL_CHUNK;
+    const int end = min(c.seg_len[seg], off + SEL_CHUNK);
+    const float* s = score + c.seg_start[seg];
+    uint8_t* kp = keep + c.seg_start[seg];
+    if (st.keep_none) {
+        for (int j = off + tid; j < end; j += SEL_THREADS) kp[j] = 0;
+        return;
+    }
+    const int64_t tb = ws.chunk_tie_base[ch];
+    const int eq_total = ws.chunk_eq[ch];
+    if (eq_total == 0 || tb + eq_total <= st.tie_quota) {        // every tie of this chunk survives
+        for (int j = off + tid; j < end; j += SEL_THREADS) kp[j] = key_of_score(s[j]) >= st.thr_key;
+        return;
+    }
+    if (tb >= st.tie_quota) {                                     // no tie of this chunk survives
+        for (int j = off + tid; j < end; j += SEL_THREADS) kp[j] = key_of_score(s[j]) > st.thr_key;
+        return;
+    }
+    // the quota runs out inside this chunk: rank the ties in order
+    int64_t running = tb;
+    for (int base = off; base < end; base += SEL_THREADS) {       // uniform trip count
+        const int j = base + tid;
+        uint32_t key = 0;
+        int is_eq = 0;
+        if (j < end) {
+            key = key_of_score(s[j]);
+            is_eq = key == st.thr_key;
+        }
+        int32_t tot;
+        int32_t ex = block_excl_scan<int32_t>(is_eq, lds32, &tot);
+        if (j < end) kp[j] = key > st.thr_key || (is_eq && running + ex < st.tie_quota);
+        running += tot;
+    }
+}
+
+kvtrim_status launch_select(kvtrim_ctx* ctx, const CacheView& c, const float* score, const int64_t* budget,
+                            uint8_t* keep, int32_t* kept, uint32_t* thr, hipStream_t st) {
+    const Shape& sh = ctx->shape;
+    const Workspace& ws = ctx->ws;
+    const int64_t max_chunks = c.cap / SEL_CHUNK + sh.nseg;      // bound on the chunk count
+    const int n_chunk_blocks = (int)max_chunks;
+    const int hist_blocks = (int)(max_chunks < 1024 ? (max_chunks < 1 ? 1 : max_chunks) : 1024);
+    hipLaunchKernelGGL(k_sel_plan, dim3(1), dim3(1024), 0, st, c, sh, budget, ws, kept);
+    hipLaunchKernelGGL(k_sel_hist<0>, dim3(hist_blocks), dim3(SEL_THREADS), 0, st, c, score, sh, ws, thr);
+    hipLaunchKernelGGL(k_sel_hist<1>, dim3(hist_blocks), dim3(SEL_THREADS), 0, st, c, score, sh, ws, thr);
+    hipLaunchKernelGGL(k_sel_hist<2>, dim3(hist_blocks), dim3(SEL_THREADS), 0, st, c, score, sh, ws, thr);
+    hipLaunchKernelGGL(k_sel_count, dim3(n_chunk_blocks), dim3(CNT_THREADS), 0, st, c, score, sh, ws, kept);
+    hipLaunchKernelGGL(k_sel_mask, dim3(n_chunk_blocks), dim3(SEL_THREADS), 0, st, c, score, sh, ws, keep);
+    KVTRIM_HIP(ctx, hipGetLastError());
+    return KVTRIM_OK;
+}
+
+}  // namespace kvtrim

@@ -1,0 +1,258 @@
+// C ABI of libkvtrim: argument checks, workspace, and dispatch to the kernel launchers.
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "kvtrim_internal.h"
+
+namespace kvtrim {
+
+kvtrim_status hip_fail(kvtrim_ctx* ctx, hipError_t e, const char* what) {
+    if (ctx) snprintf(ctx->last_error, sizeof(ctx->last_error), "%s: %s", what, hipGetErrorString(e));
+    return KVTRIM_EHIP;
+}
+
+static kvtrim_status invalid(kvtrim_ctx* ctx, const char* why) {
+    if (ctx) snprintf(ctx->last_error, sizeof(ctx->last_error), "invalid argument: %s", why);
+    return KVTRIM_EINVAL;
+}
+
+static bool config_ok(const kvtrim_config* c) {
+    if (!c) return false;
+    if (c->n_seq < 1 || c->n_layers < 1 || c->n_kv_heads < 1 || c->n_q_heads < 1) return false;
+    if (c->n_q_heads % c->n_kv_heads) return false;
+    const int g = c->n_q_heads / c->n_kv_heads;
+    if (g < 1 || g > 8) return false;
+    if (c->head_dim != 64 && c->head_dim != 128) return false;
+    if (c->max_entries < 1 || c->max_entries > ((int64_t)1 << 31) - 1) return false;
+    const int64_t nseg = (int64_t)c->n_seq * c->n_layers * c->n_kv_heads;
+    if (nseg > (1 << 24) || c->n_seq > 65536) return false;
+    return true;
+}
+
+struct Layout {
+    size_t off[16];
+    size_t total;
+    int64_t max_sel_chunks, max_cmp_chunks, max_att_chunks;
+};
+
+static size_t bump(size_t& cur, size_t bytes) {
+    size_t at = (cur + 255) & ~(size_t)255;
+    cur = at + bytes;
+    return at;
+}
+
+static Layout layout_of(const kvtrim_config* c) {
+    Layout l;
+    const int64_t nseg = (int64_t)c->n_seq * c->n_layers * c->n_kv_heads;
+    const int G = c->n_q_heads / c->n_kv_heads;
+    l.max_sel_chunks = c->max_entries / SEL_CHUNK + nseg;
+    l.max_cmp_chunks = c->max_entries / CMP_CHUNK + nseg;
+    // the attention chunk grows with the capacity (att_chunk_for) so that at most 16384 full
+    // chunks plus one ragged tail per segment ever exist
+    const int64_t full = c->max_entries / 256 < 16384 ? c->max_entries / 256 : 16384;
+    const int64_t att = full + nseg + 1;
+    l.max_att_chunks = att;
+    size_t cur = 0;
+    l.off[0] = bump(cur, (nseg + 1) * sizeof(int32_t));                        // sel_chunk_prefix
+    l.off[1] = bump(cur, l.max_sel_chunks * sizeof(int32_t));                  // sel_chunk_seg
+    l.off[2] = bump(cur, (size_t)3 * c->n_seq * RADIX_BINS * sizeof(uint32_t)); // hist
+    l.off[3] = bump(cur, (size_t)c->n_seq * sizeof(SelState));                 // sel
+    l.off[4] = bump(cur, 8 * sizeof(uint32_t));                                // done
+    l.off[5] = bump(cur, l.max_sel_chunks * sizeof(int32_t));                  // chunk_eq
+    l.off[6] = bump(cur, l.max_sel_chunks * sizeof(int64_t));                  // chunk_tie_base
+    l.off[7] = bump(cur, (nseg + 1) * sizeof(int32_t));                        // cmp_chunk_prefix
+    l.off[8] = bump(cur, l.max_cmp_chunks * sizeof(int32_t));                  // cmp_chunk_seg
+    l.off[9] = bump(cur, l.max_cmp_chunks * sizeof(int64_t));                  // cmp_chunk_dst
+    l.off[10] = bump(cur, (nseg + 1) * sizeof(int32_t));                       // att_chunk_prefix
+    l.off[11] = bump(cur, l.max_att_chunks * sizeof(int32_t));                 // att_chunk_seg
+    l.off[12] = bump(cur, (size_t)l.max_att_chunks * G * (c->head_dim + 2) * sizeof(float)); // att_partial
+    l.off[13] = bump(cur, 256);                                                // err
+    l.total = (cur + 255) & ~(size_t)255;
+    return l;
+}
+
+static CacheView view_of(const kvtrim_cache* c) {
+    CacheView v;
+    v.k = (const uint16_t*)c->k;
+    v.v = (const uint16_t*)c->v;
+    v.log_beta = c->log_beta;
+    v.pos = c->pos;
+    v.seg_start = c->seg_start;
+    v.seg_len = c->seg_len;
+    v.cap = c->cap_entries;
+    return v;
+}
+
+static CacheViewMut view_mut_of(const kvtrim_cache* c) {
+    CacheViewMut v;
+    v.k = (uint16_t*)c->k;
+    v.v = (uint16_t*)c->v;
+    v.log_beta = c->log_beta;
+    v.pos = c->pos;
+    v.seg_start = c->seg_start;
+    v.seg_len = c->seg_len;
+    v.cap = c->cap_entries;
+    return v;
+}
+
+static const char* cache_problem(const kvtrim_ctx* ctx, const kvtrim_cache* c, bool need_rows) {
+    if (!c) return "cache is NULL";
+    if (!c->log_beta || !c->pos || !c->seg_start || !c->seg_len) return "cache has a NULL metadata pointer";
+    if (need_rows && (!c->k || !c->v)) return "cache has a NULL k/v pointer";
+    if (need_rows && ((((uintptr_t)c->k) | ((uintptr_t)c->v)) & 15)) return "k/v not 16-byte aligned";
+    if (c->cap_entries < 1 || c->cap_entries > ctx->cfg.max_entries) return "cap_entries outside [1, max_entries]";
+    return nullptr;
+}
+
+}  // namespace kvtrim
+
+using namespace kvtrim;
+
+extern "C" {
+
+size_t kvtrim_workspace_bytes(const kvtrim_config* cfg) {
+    if (!config_ok(cfg)) return 0;
+    return layout_of(cfg).total;
+}
+
+kvtrim_status kvtrim_create(kvtrim_ctx** out, const kvtrim_config* cfg) {
+    if (!out) return KVTRIM_EINVAL;
+    *out = nullptr;
+    if (!config_ok(cfg)) return KVTRIM_EINVAL;
+    kvtrim_ctx* ctx = new (std::nothrow) kvtrim_ctx;
+    if (!ctx) return KVTRIM_ENOMEM;
+    memset(ctx, 0, sizeof(*ctx));
+    ctx->cfg = *cfg;
+    Shape& sh = ctx->shape;
+    sh.n_seq = cfg->n_seq;
+    sh.n_layers = cfg->n_layers;
+    sh.n_kv_heads = cfg->n_kv_heads;
+    sh.n_q_heads = cfg->n_q_heads;
+    sh.head_dim = cfg->head_dim;
+    sh.segs_per_seq = cfg->n_layers * cfg->n_kv_heads;
+    sh.nseg = cfg->n_seq * sh.segs_per_seq;
+    sh.group = cfg->n_q_heads / cfg->n_kv_heads;
+    const Layout l = layout_of(cfg);
+    ctx->ws_bytes = l.total;
+    if (hipGetDevice(&ctx->device) != hipSuccess || hipMalloc(&ctx->ws_base, l.total) != hipSuccess) {
+        (void)hipGetLastError();
+        delete ctx;
+        return KVTRIM_ENOMEM;
+    }
+    if (hipHostMalloc((void**)&ctx->err_host, sizeof(int32_t), hipHostMallocDefault) != hipSuccess ||
+        hipMemset(ctx->ws_base, 0, l.total) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+        (void)hipGetLastError();
+        if (ctx->err_host) (void)hipHostFree(ctx->err_host);
+        (void)hipFree(ctx->ws_base);
+        delete ctx;
+        return KVTRIM_EHIP;
+    }
+    char* b = (char*)ctx->ws_base;
+    Workspace& w = ctx->ws;
+    w.sel_chunk_prefix = (int32_t*)(b + l.off[0]);
+    w.sel_chunk_seg = (int32_t*)(b + l.off[1]);
+    w.hist = (uint32_t*)(b + l.off[2]);
+    w.sel = (SelState*)(b + l.off[3]);
+    w.done = (uint32_t*)(b + l.off[4]);
+    w.chunk_eq = (int32_t*)(b + l.off[5]);
+    w.chunk_tie_base = (int64_t*)(b + l.off[6]);
+    w.cmp_chunk_prefix = (int32_t*)(b + l.off[7]);
+    w.cmp_chunk_seg = (int32_t*)(b + l.off[8]);
+    w.cmp_chunk_dst = (int64_t*)(b + l.off[9]);
+    w.att_chunk_prefix = (int32_t*)(b + l.off[10]);
+    w.att_chunk_seg = (int32_t*)(b + l.off[11]);
+    w.att_partial = (float*)(b + l.off[12]);
+    w.err = (int32_t*)(b + l.off[13]);
+    w.max_sel_chunks = l.max_sel_chunks;
+    w.max_cmp_chunks = l.max_cmp_chunks;
+    w.max_att_chunks = l.max_att_chunks;
+    *out = ctx;
+    return KVTRIM_OK;
+}
+
+kvtrim_status kvtrim_destroy(kvtrim_ctx* ctx) {
+    if (!ctx) return KVTRIM_EINVAL;
+    (void)hipDeviceSynchronize();
+    if (ctx->err_host) (void)hipHostFree(ctx->err_host);
+    if (ctx->ws_base) (void)hipFree(ctx->ws_base);
+    delete ctx;
+    return KVTRIM_OK;
+}
+
+const char* kvtrim_last_error(const kvtrim_ctx* ctx) { return ctx ? ctx->last_error : "no context"; }
+
+kvtrim_status kvtrim_poll_error(kvtrim_ctx* ctx, void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    KVTRIM_HIP(ctx, hipMemcpyAsync(ctx->err_host, ctx->ws.err, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    KVTRIM_HIP(ctx, hipStreamSynchronize(st));
+    const int32_t e = *ctx->err_host;
+    if (e) {
+        *ctx->err_host = 0;
+        KVTRIM_HIP(ctx, hipMemcpyAsync(ctx->ws.err, ctx->err_host, sizeof(int32_t), hipMemcpyHostToDevice, st));
+        KVTRIM_HIP(ctx, hipStreamSynchronize(st));
+    }
+    if (e & ERR_LAYOUT) return KVTRIM_ELAYOUT;
+    if (e & ERR_CAP) return KVTRIM_ECAP;
+    if (e & ERR_MISMATCH) return KVTRIM_EMISMATCH;
+    return KVTRIM_OK;
+}
+
+kvtrim_status kvtrim_score(kvtrim_ctx* ctx, const kvtrim_cache* c, const int32_t* now, float* score_out,
+                           void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    if (const char* p = cache_problem(ctx, c, false)) return invalid(ctx, p);
+    if (!now || !score_out) return invalid(ctx, "now / score_out is NULL");
+    return launch_score(ctx, view_of(c), now, score_out, (hipStream_t)hip_stream);
+}
+
+kvtrim_status kvtrim_select_global(kvtrim_ctx* ctx, const kvtrim_cache* c, const float* score,
+                                   const int64_t* budget, uint8_t* keep_out, int32_t* kept_out,
+                                   uint32_t* thr_key_out, void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    if (const char* p = cache_problem(ctx, c, false)) return invalid(ctx, p);
+    if (!score || !budget || !keep_out || !kept_out) return invalid(ctx, "score / budget / keep_out / kept_out is NULL");
+    return launch_select(ctx, view_of(c), score, budget, keep_out, kept_out, thr_key_out, (hipStream_t)hip_stream);
+}
+
+kvtrim_status kvtrim_compact(kvtrim_ctx* ctx, const kvtrim_cache* src, const uint8_t* keep, const int32_t* kept,
+                             kvtrim_cache* dst, int32_t reserve, void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    if (const char* p = cache_problem(ctx, src, true)) return invalid(ctx, p);
+    if (const char* p = cache_problem(ctx, dst, true)) return invalid(ctx, p);
+    if (!keep || !kept) return invalid(ctx, "keep / kept is NULL");
+    if (reserve < 0) return invalid(ctx, "reserve < 0");
+    if (src->k == dst->k || src->v == dst->v || src->log_beta == dst->log_beta || src->pos == dst->pos ||
+        src->seg_start == dst->seg_start || src->seg_len == dst->seg_len)
+        return invalid(ctx, "src and dst share a buffer");
+    return launch_compact(ctx, view_of(src), keep, kept, view_mut_of(dst), reserve, (hipStream_t)hip_stream);
+}
+
+kvtrim_status kvtrim_decode_attn(kvtrim_ctx* ctx, const kvtrim_cache* c, const void* q, int32_t layer_begin,
+                                 int32_t layer_end, float softmax_scale, float* out, float* lse,
+                                 void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    if (const char* p = cache_problem(ctx, c, true)) return invalid(ctx, p);
+    if (!q || !out) return invalid(ctx, "q / out is NULL");
+    if (((uintptr_t)q) & 15) return invalid(ctx, "q not 16-byte aligned");
+    if (layer_begin < 0 || layer_end > ctx->cfg.n_layers || layer_begin >= layer_end)
+        return invalid(ctx, "empty or out-of-range layer range");
+    if (!(softmax_scale == softmax_scale)) return invalid(ctx, "softmax_scale is NaN");
+    return launch_attn(ctx, view_of(c), (const uint16_t*)q, layer_begin, layer_end, softmax_scale, out, lse,
+                       (hipStream_t)hip_stream);
+}
+
+kvtrim_status kvtrim_append(kvtrim_ctx* ctx, kvtrim_cache* c, const void* k_new, const void* v_new,
+                            const float* log_beta_new, const int32_t* pos_new, int32_t n_new, void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    if (const char* p = cache_problem(ctx, c, true)) return invalid(ctx, p);
+    if (!k_new || !v_new || !log_beta_new || !pos_new) return invalid(ctx, "a new-token pointer is NULL");
+    if ((((uintptr_t)k_new) | ((uintptr_t)v_new)) & 15) return invalid(ctx, "k_new / v_new not 16-byte aligned");
+    if (n_new < 1) return invalid(ctx, "n_new < 1");
+    return launch_append(ctx, view_mut_of(c), (const uint16_t*)k_new, (const uint16_t*)v_new, log_beta_new,
+                         pos_new, n_new, (hipStream_t)hip_stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,127 @@
+// Internal declarations shared by the translation units of libkvtrim (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kvtrim.h"
+
+namespace kvtrim {
+
+// Chunk sizes (entries of one segment handled as a unit).
+constexpr int SEL_CHUNK = 2048;      // selection: 256 threads x 8 entries
+constexpr int CMP_CHUNK = 256;       // compaction: 256 threads, 64 entries per wave
+constexpr int RADIX_BITS0 = 11, RADIX_BITS1 = 11, RADIX_BITS2 = 10;
+constexpr int RADIX_BINS = 2048;     // bins of the widest pass
+
+constexpr int ERR_CAP = 1;           // bits of the sticky device flag
+constexpr int ERR_MISMATCH = 2;
+constexpr int ERR_LAYOUT = 4;
+
+struct Shape {
+    int32_t n_seq, n_layers, n_kv_heads, n_q_heads, head_dim;
+    int32_t nseg, segs_per_seq, group;
+};
+
+struct CacheView {                   // device pointers, passed by value to kernels
+    const uint16_t* k;
+    const uint16_t* v;
+    const float* log_beta;
+    const int32_t* pos;
+    const int64_t* seg_start;
+    const int32_t* seg_len;
+    int64_t cap;
+};
+
+struct CacheViewMut {
+    uint16_t* k;
+    uint16_t* v;
+    float* log_beta;
+    int32_t* pos;
+    int64_t* seg_start;
+    int32_t* seg_len;
+    int64_t cap;
+};
+
+// Per-sequence state of the radix select, kept in the workspace.
+struct SelState {
+    uint32_t prefix;     // digits fixed so far (right aligned)
+    uint32_t thr_key;    // final threshold key
+    int64_t count;       // candidates of the sequence
+    int64_t want;        // min(budget, count)
+    int64_t rank;        // entries still to take inside the current bucket
+    int64_t tie_quota;   // entries equal to thr_key to keep (in storage order)
+    int32_t keep_none;   // want == 0
+    int32_t pad;
+};
+
+struct Workspace {
+    // selection
+    int32_t* sel_chunk_prefix;   // [nseg+1] first chunk of each segment
+    int32_t* sel_chunk_seg;      // [max_sel_chunks] segment of each chunk
+    uint32_t* hist;              // [3][n_seq][RADIX_BINS]
+    SelState* sel;               // [n_seq]
+    uint32_t* done;              // [8] "last block" counters
+    int32_t* chunk_eq;           // [max_sel_chunks] entries equal to the threshold
+    int64_t* chunk_tie_base;     // [max_sel_chunks] ties of the sequence before the chunk
+    // compaction
+    int32_t* cmp_chunk_prefix;   // [nseg+1]
+    int32_t* cmp_chunk_seg;      // [max_cmp_chunks]
+    int64_t* cmp_chunk_dst;      // [max_cmp_chunks] first dst entry of the chunk's survivors
+    // attention
+    int32_t* att_chunk_prefix;   // [nseg+1]
+    int32_t* att_chunk_seg;      // [max_att_chunks]
+    float* att_partial;          // [max_att_chunks][G][D+2]  (m, l, o[D]) per query head
+    int32_t* err;                // sticky device flag
+    int64_t max_sel_chunks, max_cmp_chunks, max_att_chunks;
+};
+
+}  // namespace kvtrim
+
+struct kvtrim_ctx {
+    kvtrim_config cfg;
+    kvtrim::Shape shape;
+    kvtrim::Workspace ws;
+    void* ws_base;
+    size_t ws_bytes;
+    int32_t* err_host;           // pinned mirror of the device flag
+    int device;
+    char last_error[256];
+};
+
+namespace kvtrim {
+
+// Upper bound on attention chunks for a cache of `cap` entries, and the chunk size used.
+int att_chunk_for(const kvtrim_ctx* ctx, int64_t cap);
+
+kvtrim_status launch_score(kvtrim_ctx*, const CacheView&, const int32_t* now, float* score, hipStream_t);
+kvtrim_status launch_select(kvtrim_ctx*, const CacheView&, const float* score, const int64_t* budget,
+                            uint8_t* keep, int32_t* kept, uint32_t* thr, hipStream_t);
+kvtrim_status launch_compact(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const int32_t* kept,
+                             const CacheViewMut& dst, int32_t reserve, hipStream_t);
+kvtrim_status launch_attn(kvtrim_ctx*, const CacheView&, const uint16_t* q, int32_t layer_begin,
+                          int32_t layer_end, float scale, float* out, float* lse, hipStream_t);
+kvtrim_status launch_append(kvtrim_ctx*, const CacheViewMut&, const uint16_t* k_new, const uint16_t* v_new,
+                            const float* lb_new, const int32_t* pos_new, int32_t n_new, hipStream_t);
+
+kvtrim_status hip_fail(kvtrim_ctx* ctx, hipError_t e, const char* what);
+
+#define KVTRIM_HIP(ctx, expr)                                          \
+    do {                                                               \
+        hipError_t _e = (expr);                                        \
+        if (_e != hipSuccess) return ::kvtrim::hip_fail(ctx, _e, #expr); \
+    } while (0)
+
+// ---- device helpers --------------------------------------------------------------------
+__device__ __forceinline__ uint32_t key_of_score(float s) {
+    uint32_t u = __float_as_uint(s);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+// number of set bits of `mask` below this lane
+__device__ __forceinline__ int mbcnt(uint64_t mask) {
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
+}
+
+}  // namespace kvtrim

@@ -1,0 +1,269 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Selection and compaction must match bit for bit; attention within
+max|o_gpu - o_ref| / max|o_ref| <= 5e-3 (bf16 inputs, fp32 accumulation).
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import kvtrim_inputs as ki
+import oracle
+import paper_2605_09649_amd as kv
+from harness import attn_error, compare_caches, device_cache_to_host, run_steps_both
+from helpers import bf16_bits, host_cache, live_mask
+
+pytestmark = pytest.mark.gpu
+ATTN_TOL = 5e-3
+DEV = "cuda:0"
+
+
+def check(results):
+    for i, r in enumerate(results):
+        assert r["status"] == 0, (i, r)
+        assert r["score_equal"], (i, "score bits differ")
+        assert r["keep_equal"], (i, "selection differs")
+        assert r["cache_equal"], (i, "compacted cache differs")
+        assert r["attn_err"] <= ATTN_TOL, (i, r["attn_err"])
+        assert r["lse_err"] <= 2e-3 and r["lse_inf_equal"], (i, r)
+
+
+def wl(S, L, H, G, D, name="t"):
+    return ki.Workload(name, 0, S, L, H, G * H, D, (0,) * S, (0,) * S, 1, 3.0, 1.5)
+
+
+# ---------------------------------------------------------------------------------- whole loop
+
+def test_tiny_workload_full_loop():
+    w = ki.workload("tiny")                       # L4 H4 G2 D64, 2048 prefilled, B = 1024, 16 steps
+    check(run_steps_both(w, steps=16, budget=w.budget, device=DEV))
+
+
+@pytest.mark.parametrize("name,prefill,steps", [("llama", 700, 3), ("long", 900, 3), ("vlm", 640, 3),
+                                                ("multiturn", 600, 2)])
+def test_scaled_down_workloads(name, prefill, steps):
+    w = ki.workload(name, prefill=prefill)
+    check(run_steps_both(w, steps=steps, budget=w.budget, device=DEV))
+
+
+@pytest.mark.parametrize("S,L,H,G,D", [(1, 2, 2, 1, 128), (2, 2, 1, 7, 128), (1, 1, 3, 8, 64), (3, 1, 2, 3, 64),
+                                       (1, 2, 2, 5, 128), (1, 1, 2, 6, 128)])
+def test_ragged_segments_spanning_several_chunks(S, L, H, G, D):
+    w = wl(S, L, H, G, D)
+    rng = np.random.default_rng(S * 1000 + G * 10 + D)
+    seg_len = rng.integers(0, 6000, w.nseg)
+    seg_len[rng.integers(0, w.nseg)] = 0          # an empty segment
+    seg_len[rng.integers(0, w.nseg)] = 2048 * 2 + 1
+    c, now = ki.ragged_cache(w, seg_len, reserve=1, salt=G)
+    per_seq = [int(seg_len[s * L * H:(s + 1) * L * H].sum()) for s in range(S)]
+    budget = [max(1, n // 3) for n in per_seq]
+    check(run_steps_both(w, steps=2, budget=budget, device=DEV, cache_dict=c, now0=now.numpy()))
+
+
+def test_one_giant_segment_and_many_empty_ones():
+    w = wl(1, 2, 4, 4, 128)
+    seg_len = [0, 0, 0, 70001, 0, 0, 3, 0]
+    c, now = ki.ragged_cache(w, seg_len, reserve=1, salt=3)
+    check(run_steps_both(w, steps=2, budget=[20011], device=DEV, cache_dict=c, now0=now.numpy()))
+
+
+# ---------------------------------------------------------------------------------- degenerate budgets, ties
+
+def run_select_compact(w, c, now, budget, score_override=None, reserve=1):
+    """One score -> select -> compact on both sides; returns (gpu results, oracle results)."""
+    hc = host_cache(w, c)
+    total = int(hc.seg_len.sum())
+    dst_cap = min(int(sum(budget)), total) + w.nseg * reserve + 4
+    ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, max(hc.cap, dst_cap))
+    src = kv.Cache.from_dict(c, DEV)
+    dst = kv.Cache.empty(w.nseg, w.head_dim, dst_cap, DEV)
+    score = torch.zeros(hc.cap, dtype=torch.float32, device=DEV)
+    keep = torch.full((hc.cap,), 7, dtype=torch.uint8, device=DEV)
+    kept = torch.zeros(w.nseg, dtype=torch.int32, device=DEV)
+    thr = torch.zeros(w.n_seq, dtype=torch.int32, device=DEV)
+    kv.kvtrim_score(ctx, src, now.to(DEV), score)
+    score_ref = oracle.score(hc, now.numpy())
+    if score_override is not None:
+        score_ref = score_override.copy()
+        score.copy_(torch.from_numpy(score_override))
+    b = torch.tensor(budget, dtype=torch.int64, device=DEV)
+    kv.kvtrim_select_global(ctx, src, score, b, keep, kept, thr)
+    kv.kvtrim_compact(ctx, src, keep, kept, dst, reserve)
+    assert kv.kvtrim_poll_error(ctx) == 0
+    keep_ref, kept_ref, thr_ref = oracle.select(hc, score_ref, np.array(budget, np.int64))
+    dst_ref = oracle.compact(hc, keep_ref, dst_cap, reserve)
+    live = live_mask(hc)
+    assert np.array_equal(score.cpu().numpy()[live].view(np.uint32), score_ref[live].view(np.uint32))
+    assert np.array_equal(keep.cpu().numpy()[live], keep_ref[live])
+    assert np.array_equal(kept.cpu().numpy(), kept_ref)
+    assert np.array_equal(thr.cpu().numpy().view(np.uint32), thr_ref)
+    assert compare_caches(device_cache_to_host(w, dst), dst_ref)
+    return kept_ref
+
+
+@pytest.mark.parametrize("frac", [0.0, 1.0, 2.0, 0.5])
+def test_budget_zero_full_and_above_full(frac):
+    w = wl(2, 2, 2, 2, 64)
+    rng = np.random.default_rng(11)
+    seg_len = rng.integers(0, 3000, w.nseg)
+    c, now = ki.ragged_cache(w, seg_len, salt=5)
+    per_seq = [int(seg_len[s * 4:(s + 1) * 4].sum()) for s in range(2)]
+    kept = run_select_compact(w, c, now, [int(frac * n) for n in per_seq])
+    for s in range(2):
+        assert kept[s * 4:(s + 1) * 4].sum() == min(int(frac * per_seq[s]), per_seq[s])
+
+
+def test_all_scores_equal_keeps_the_first_entries_in_storage_order():
+    w = wl(1, 2, 2, 2, 64)
+    seg_len = [3000, 2500, 4100, 100]
+    c, now = ki.ragged_cache(w, seg_len, salt=6)
+    score = np.full(sum(seg_len) + 4, -3.0, np.float32)
+    for B in (1, 2999, 3000, 3001, 5500, 7777, 9699, 9700):
+        kept = run_select_compact(w, c, now, [B], score_override=score)
+        expect, left = [], B
+        for n in seg_len:
+            expect.append(min(n, left))
+            left -= expect[-1]
+        assert kept.tolist() == expect
+
+
+def test_heavy_ties_signed_zeros_and_infinities():
+    w = wl(2, 1, 3, 2, 64)
+    rng = np.random.default_rng(12)
+    seg_len = rng.integers(1000, 5000, w.nseg)
+    c, now = ki.ragged_cache(w, seg_len, salt=7)
+    cap = int(seg_len.sum()) + w.nseg
+    vals = np.array([-np.inf, -7.5, -7.5, -1e-20, -0.0, 0.0, -2.0000002, -2.0], np.float32)
+    score = rng.choice(vals, size=cap).astype(np.float32)
+    for frac in (0.1, 0.37, 0.5, 0.93):
+        budget = [int(frac * seg_len[:3].sum()), int(frac * seg_len[3:].sum())]
+        run_select_compact(w, c, now, budget, score_override=score)
+
+
+def test_keys_differing_only_in_low_bits():
+    w = wl(1, 1, 2, 2, 64)
+    seg_len = [5000, 5000]
+    c, now = ki.ragged_cache(w, seg_len, salt=8)
+    rng = np.random.default_rng(13)
+    bits = (np.float32(-1.5).view(np.uint32) + rng.integers(0, 1 << 9, sum(seg_len) + 2).astype(np.uint32))
+    score = bits.view(np.float32)
+    for B in (1, 100, 4999, 9000):
+        run_select_compact(w, c, now, [B], score_override=score)
+
+
+# ---------------------------------------------------------------------------------- attention alone
+
+@pytest.mark.parametrize("D,G", [(128, 4), (128, 7), (64, 2), (128, 1), (64, 8)])
+def test_attention_against_oracle_and_layer_ranges(D, G):
+    w = wl(2, 3, 2, G, D)
+    rng = np.random.default_rng(D + G)
+    seg_len = rng.integers(0, 1500, w.nseg)
+    seg_len[0] = 0
+    seg_len[1] = 1
+    seg_len[2] = 257
+    c, _ = ki.ragged_cache(w, seg_len, salt=9)
+    hc = host_cache(w, c)
+    dc = kv.Cache.from_dict(c, DEV)
+    ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, D, hc.cap)
+    q = ki.decode_inputs(w, 0)["q"]
+    scale = 1.0 / math.sqrt(D)
+    ref, ref_lse = oracle.attend(hc, bf16_bits(q), scale)
+    out = torch.full(ref.shape, 99.0, dtype=torch.float32, device=DEV)
+    lse = torch.full(ref_lse.shape, 99.0, dtype=torch.float32, device=DEV)
+    kv.kvtrim_decode_attn(ctx, dc, q.to(DEV), 0, w.n_layers, scale, out, lse)
+    assert kv.kvtrim_poll_error(ctx) == 0
+    assert attn_error(out.cpu().numpy(), ref) <= ATTN_TOL
+    o = out.cpu().numpy()
+    assert np.all(o[0, 0, :G] == 0.0)                                   # empty segment
+    assert np.isneginf(lse.cpu().numpy()[0, 0, :G]).all()
+    fin = np.isfinite(ref_lse)
+    assert np.abs(lse.cpu().numpy()[fin] - ref_lse[fin]).max() <= 2e-3
+    # a layer range writes only its layers
+    out2 = torch.full(ref.shape, 99.0, dtype=torch.float32, device=DEV)
+    kv.kvtrim_decode_attn(ctx, dc, q.to(DEV), 1, 2, scale, out2, None)
+    o2 = out2.cpu().numpy()
+    assert np.all(o2[:, 0] == 99.0) and np.all(o2[:, 2] == 99.0)
+    assert np.array_equal(o2[:, 1], o[:, 1])
+
+
+def test_attention_with_large_logits_stays_finite():
+    w = wl(1, 1, 1, 4, 128)
+    c, _ = ki.ragged_cache(w, [900], salt=10)
+    c["k"] *= 6.0
+    hc = host_cache(w, c)
+    q = ki.decode_inputs(w, 1)["q"] * 6.0
+    ctx = kv.Context(1, 1, 1, 4, 128, hc.cap)
+    ref, _ = oracle.attend(hc, bf16_bits(q), 1.0)
+    out = torch.zeros(ref.shape, dtype=torch.float32, device=DEV)
+    kv.kvtrim_decode_attn(ctx, kv.Cache.from_dict(c, DEV), q.to(DEV), 0, 1, 1.0, out, None)
+    o = out.cpu().numpy()
+    assert np.isfinite(o).all() and attn_error(o, ref) <= ATTN_TOL
+
+
+# ---------------------------------------------------------------------------------- error paths (kernels exit normally)
+
+def test_device_side_errors_are_reported_and_nothing_overflows():
+    w = wl(1, 1, 4, 2, 64)
+    seg_len = [300, 10, 0, 500]
+    c, now = ki.ragged_cache(w, seg_len, reserve=1, salt=14)
+    cap = sum(seg_len) + 4
+    ctx = kv.Context(1, 1, 4, 8, 64, cap)
+    src = kv.Cache.from_dict(c, DEV)
+    keep = torch.ones(cap, dtype=torch.uint8, device=DEV)
+    kept = torch.tensor(seg_len, dtype=torch.int32, device=DEV)
+    small = kv.Cache.empty(4, 64, 700, DEV)
+    small.k.fill_(1.0)
+    kv.kvtrim_compact(ctx, src, keep, kept, small, 1)
+    assert kv.kvtrim_poll_error(ctx) == -4                               # KVTRIM_ECAP
+    assert torch.all(small.k == 1.0)                                     # nothing was written
+    assert kv.kvtrim_poll_error(ctx) == 0                                # flag cleared
+    big = kv.Cache.empty(4, 64, cap, DEV)
+    wrong = kept.clone()
+    wrong[0] -= 1
+    kv.kvtrim_compact(ctx, src, keep, wrong, big, 1)
+    assert kv.kvtrim_poll_error(ctx) == -5                               # KVTRIM_EMISMATCH
+    # appending two tokens where one slot is reserved
+    new = ki.decode_inputs(w, 0)
+    two = lambda t: torch.stack([t, t], 1).contiguous().to(DEV)
+    before = src.seg_len.clone()
+    kv.kvtrim_append(ctx, src, two(new["k_new"]), two(new["v_new"]), two(new["log_beta_new"]),
+                     torch.zeros(4, 2, dtype=torch.int32, device=DEV), 2)
+    assert kv.kvtrim_poll_error(ctx) == -4
+    assert torch.equal(src.seg_len, before)
+    # an inconsistent segment table
+    bad = kv.Cache(src.k, src.v, src.log_beta, src.pos, src.seg_start, torch.tensor([300, 10, 0, 900], dtype=torch.int32, device=DEV))
+    score = torch.zeros(cap, dtype=torch.float32, device=DEV)
+    kv.kvtrim_score(ctx, bad, now.to(DEV), score)
+    kv.kvtrim_select_global(ctx, bad, score, torch.tensor([5], dtype=torch.int64, device=DEV), keep, kept)
+    assert kv.kvtrim_poll_error(ctx) == -6                               # KVTRIM_ELAYOUT
+
+
+def test_host_side_argument_checks():
+    ctx = kv.Context(1, 1, 2, 4, 64, 100)
+    c = kv.Cache.empty(2, 64, 100, DEV)
+    too_big = kv.Cache.empty(2, 64, 101, DEV)
+    score = torch.zeros(101, dtype=torch.float32, device=DEV)
+    now = torch.zeros(1, dtype=torch.int32, device=DEV)
+    with pytest.raises(kv.KvtrimError) as e:
+        kv.kvtrim_score(ctx, too_big, now, score)
+    assert e.value.status == -1
+    keep = torch.zeros(100, dtype=torch.uint8, device=DEV)
+    kept = torch.zeros(2, dtype=torch.int32, device=DEV)
+    with pytest.raises(kv.KvtrimError):
+        kv.kvtrim_compact(ctx, c, keep, kept, c, 1)                      # src == dst
+    q = torch.zeros(1, 1, 4, 64, dtype=torch.bfloat16, device=DEV)
+    out = torch.zeros(1, 1, 4, 64, dtype=torch.float32, device=DEV)
+    with pytest.raises(kv.KvtrimError):
+        kv.kvtrim_decode_attn(ctx, c, q, 0, 2, 0.125, out)               # layer range beyond L
+    with pytest.raises(kv.KvtrimError):
+        kv.Context(1, 1, 2, 4, 96, 100)
+
+
+def test_results_are_deterministic_across_runs():
+    w = ki.workload("llama", prefill=500)
+    a = run_steps_both(w, steps=2, budget=w.budget, device=DEV)
+    b = run_steps_both(w, steps=2, budget=w.budget, device=DEV)
+    check(a)
+    assert [r["attn_err"] for r in a] == [r["attn_err"] for r in b]
