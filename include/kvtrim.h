@@ -150,6 +150,22 @@ kvtrim_status kvtrim_append(kvtrim_ctx *ctx, kvtrim_cache *c, const void *k_new,
                             const float *log_beta_new, const int32_t *pos_new, int32_t n_new,
                             void *hip_stream);
 
+/* Instrumentation (for the benchmark; not a step of the method).  Between
+ * kvtrim_profile_begin and kvtrim_profile_end every launch of a kernel whose bit is
+ * set in `kernel_mask` (bit i = kernel id i, names from kvtrim_kernel_name) is
+ * bracketed by a pair of HIP events recorded on the stream the kernel is launched
+ * on.  begin allocates the event pool (host side, synchronous; at most
+ * KVTRIM_PROFILE_MAX_LAUNCHES launches are bracketed, later ones run unbracketed);
+ * end waits for `hip_stream` and writes, per kernel id, the summed duration in
+ * milliseconds and the number of bracketed launches into host arrays of
+ * KVTRIM_N_KERNELS elements.  Do not capture a HIP graph while profiling is on. */
+#define KVTRIM_N_KERNELS 13
+#define KVTRIM_PROFILE_MAX_LAUNCHES 4096
+kvtrim_status kvtrim_profile_begin(kvtrim_ctx *ctx, uint32_t kernel_mask);
+kvtrim_status kvtrim_profile_end(kvtrim_ctx *ctx, void *hip_stream, double *ms_sum_host,
+                                 int64_t *launches_host);
+const char *kvtrim_kernel_name(int32_t kernel_id); /* NULL when out of range */
+
 #ifdef __cplusplus
 }
 #endif

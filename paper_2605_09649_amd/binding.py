@@ -13,7 +13,9 @@ STATUS = {0: "KVTRIM_OK", -1: "KVTRIM_EINVAL", -2: "KVTRIM_ENOMEM", -3: "KVTRIM_
 
 EXPORTS = ["kvtrim_create", "kvtrim_destroy", "kvtrim_workspace_bytes", "kvtrim_last_error",
            "kvtrim_poll_error", "kvtrim_score", "kvtrim_select_global", "kvtrim_compact",
-           "kvtrim_decode_attn", "kvtrim_append"]
+           "kvtrim_decode_attn", "kvtrim_append", "kvtrim_profile_begin", "kvtrim_profile_end",
+           "kvtrim_kernel_name"]
+N_KERNELS = 13
 
 
 class KvtrimError(RuntimeError):
@@ -59,8 +61,12 @@ def load_library():
                                            C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.kvtrim_append.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_int32, C.c_void_p]
+        lib.kvtrim_profile_begin.argtypes = [C.c_void_p, C.c_uint32]
+        lib.kvtrim_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+        lib.kvtrim_kernel_name.argtypes = [C.c_int32]
+        lib.kvtrim_kernel_name.restype = C.c_char_p
         for name in EXPORTS:
-            if name not in ("kvtrim_workspace_bytes", "kvtrim_last_error"):
+            if name not in ("kvtrim_workspace_bytes", "kvtrim_last_error", "kvtrim_kernel_name"):
                 getattr(lib, name).restype = C.c_int
         _lib = lib
     return _lib
@@ -188,3 +194,20 @@ def kvtrim_append(ctx, cache, k_new, v_new, log_beta_new, pos_new, n_new, stream
                                              _ptr(v_new, torch.bfloat16), _ptr(log_beta_new, torch.float32),
                                              _ptr(pos_new, torch.int32), int(n_new), _stream(stream)),
            "kvtrim_append")
+
+
+def kvtrim_kernel_name(kernel_id):
+    n = load_library().kvtrim_kernel_name(int(kernel_id))
+    return n.decode() if n else None
+
+
+def kvtrim_profile_begin(ctx, kernel_mask):
+    _check(ctx, load_library().kvtrim_profile_begin(ctx.handle, int(kernel_mask)), "kvtrim_profile_begin")
+
+
+def kvtrim_profile_end(ctx, stream=None):
+    """Returns {kernel name: (summed ms, bracketed launches)} for the kernels that were launched."""
+    ms = (C.c_double * N_KERNELS)()
+    n = (C.c_int64 * N_KERNELS)()
+    _check(ctx, load_library().kvtrim_profile_end(ctx.handle, _stream(stream), ms, n), "kvtrim_profile_end")
+    return {kvtrim_kernel_name(i): (ms[i], n[i]) for i in range(N_KERNELS) if n[i] > 0}

@@ -230,11 +230,15 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
     }
 }
 
-// One block per segment of the layer range: merges the partial results of its chunks.
+// One block per segment of the layer range: merges the partial results of its chunks, a tile
+// of COMB_TILE chunks at a time (their (m, l) pairs go through LDS so that the D-wide loads of
+// a tile are independent of each other and can all be in flight).
+constexpr int COMB_TILE = 16;
 template <int D>
 __global__ __launch_bounds__(ATT_THREADS) void k_att_combine(Shape sh, Workspace ws, int layer_begin,
                                                              int layer_end, float* __restrict__ out,
                                                              float* __restrict__ lse) {
+    __shared__ float s_m[COMB_TILE][8], s_l[COMB_TILE][8];
     const int G = sh.group;
     const int nl = layer_end - layer_begin;
     const int per = nl * sh.n_kv_heads;
@@ -244,20 +248,58 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_combine(Shape sh, Workspace
     const int c0 = ws.att_chunk_prefix[seg], c1 = ws.att_chunk_prefix[seg + 1];
     const int64_t hq0 = ((int64_t)seq * sh.n_layers + layer) * sh.n_q_heads + (int64_t)head * G;
     const float LN2 = 0.6931471805599453f;
-    for (int idx = threadIdx.x; idx < G * D; idx += ATT_THREADS) {
-        const int g = idx / D, d = idx % D;
-        float M = -INFINITY;
-        for (int cc = c0; cc < c1; ++cc) M = fmaxf(M, ws.att_partial[((size_t)cc * G + g) * (D + 2)]);
-        const float Ms = M == -INFINITY ? 0.f : M;
-        float acc = 0.f, lsum = 0.f;
-        for (int cc = c0; cc < c1; ++cc) {
-            const float* p = ws.att_partial + ((size_t)cc * G + g) * (D + 2);
-            const float w = __builtin_amdgcn_exp2f(p[0] - Ms);
-            acc += p[2 + d] * w;
-            lsum += p[1] * w;
+    constexpr int PAIRS = (8 * D + ATT_THREADS - 1) / ATT_THREADS;   // (query, d) pairs per thread, G <= 8
+    float M[PAIRS], acc[PAIRS], lsum[PAIRS];
+#pragma unroll
+    for (int p = 0; p < PAIRS; ++p) {
+        M[p] = -INFINITY;
+        acc[p] = 0.f;
+        lsum[p] = 0.f;
+    }
+    const size_t stride = (size_t)G * (D + 2);
+    for (int t0 = c0; t0 < c1; t0 += COMB_TILE) {
+        const int nt = min(COMB_TILE, c1 - t0);
+        __syncthreads();
+        for (int i = threadIdx.x; i < nt * G; i += ATT_THREADS) {
+            const float* p = ws.att_partial + (size_t)(t0 + i / G) * stride + (size_t)(i % G) * (D + 2);
+            s_m[i / G][i % G] = p[0];
+            s_l[i / G][i % G] = p[1];
         }
-        out[(hq0 + g) * D + d] = lsum > 0.f ? acc / lsum : 0.f;
-        if (d == 0 && lse) lse[hq0 + g] = lsum > 0.f ? (M + __builtin_amdgcn_logf(lsum)) * LN2 : -INFINITY;
+        __syncthreads();
+#pragma unroll
+        for (int p = 0; p < PAIRS; ++p) {
+            const int idx = threadIdx.x + p * ATT_THREADS;
+            if (idx >= G * D) break;
+            const int g = idx / D, d = idx % D;
+            float tm = M[p];
+            for (int i = 0; i < nt; ++i) tm = fmaxf(tm, s_m[i][g]);
+            const float ms = tm == -INFINITY ? 0.f : tm;
+            const float a = __builtin_amdgcn_exp2f(M[p] - ms);
+            float x[COMB_TILE];
+#pragma unroll
+            for (int i = 0; i < COMB_TILE; ++i)
+                x[i] = i < nt ? ws.att_partial[(size_t)(t0 + i) * stride + (size_t)g * (D + 2) + 2 + d] : 0.f;
+            float av = acc[p] * a, lv = lsum[p] * a;
+#pragma unroll
+            for (int i = 0; i < COMB_TILE; ++i) {
+                if (i < nt) {
+                    const float w = __builtin_amdgcn_exp2f(s_m[i][g] - ms);
+                    av += x[i] * w;
+                    lv += s_l[i][g] * w;
+                }
+            }
+            acc[p] = av;
+            lsum[p] = lv;
+            M[p] = tm;
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < PAIRS; ++p) {
+        const int idx = threadIdx.x + p * ATT_THREADS;
+        if (idx >= G * D) break;
+        const int g = idx / D, d = idx % D;
+        out[(hq0 + g) * D + d] = lsum[p] > 0.f ? acc[p] / lsum[p] : 0.f;
+        if (d == 0 && lse) lse[hq0 + g] = lsum[p] > 0.f ? (M[p] + __builtin_amdgcn_logf(lsum[p])) * LN2 : -INFINITY;
     }
 }
 
@@ -278,9 +320,9 @@ static bool dispatch_partial(int G, const CacheView& c, const uint16_t* q, const
     }
 }
 
-int att_chunk_for(const kvtrim_ctx*, int64_t cap) {
+int att_chunk_for(const kvtrim_ctx* ctx, int64_t cap) {
     int64_t chunk = (cap / 16384 + 63) / 64 * 64;
-    return (int)(chunk < 256 ? 256 : chunk);
+    return (int)(chunk < ctx->att_chunk_min ? ctx->att_chunk_min : chunk);
 }
 
 kvtrim_status launch_attn(kvtrim_ctx* ctx, const CacheView& c, const uint16_t* q, int32_t layer_begin,
@@ -290,12 +332,18 @@ kvtrim_status launch_attn(kvtrim_ctx* ctx, const CacheView& c, const uint16_t* q
     const int chunk = att_chunk_for(ctx, c.cap);
     const int64_t max_chunks = c.cap / chunk + sh.nseg;
     const float scale_log2 = scale * 1.4426950408889634f;
-    hipLaunchKernelGGL(k_att_plan, dim3(1), dim3(1024), 0, st, c, sh, ws, chunk, layer_begin, layer_end, max_chunks);
-    bool ok = sh.head_dim == 128
+    { ProfScope prof(ctx, K_ATT_PLAN, st);
+      hipLaunchKernelGGL(k_att_plan, dim3(1), dim3(1024), 0, st, c, sh, ws, chunk, layer_begin, layer_end, max_chunks); }
+    bool ok;
+    {
+        ProfScope prof(ctx, K_ATT_PARTIAL, st);
+        ok = sh.head_dim == 128
                   ? dispatch_partial<128>(sh.group, c, q, sh, ws, chunk, scale_log2, (unsigned)max_chunks, st)
                   : dispatch_partial<64>(sh.group, c, q, sh, ws, chunk, scale_log2, (unsigned)max_chunks, st);
+    }
     if (!ok) return KVTRIM_EINVAL;
     const unsigned nblk = (unsigned)(sh.n_seq * (layer_end - layer_begin) * sh.n_kv_heads);
+    ProfScope prof(ctx, K_ATT_COMBINE, st);
     if (sh.head_dim == 128)
         hipLaunchKernelGGL(k_att_combine<128>, dim3(nblk), dim3(ATT_THREADS), 0, st, sh, ws, layer_begin, layer_end, out, lse);
     else

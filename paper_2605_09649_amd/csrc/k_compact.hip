@@ -92,12 +92,31 @@ __global__ __launch_bounds__(CMP_THREADS) void k_cmp_scan(CacheView src, const u
     }
 }
 
-template <int D>
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+
+template <bool NT>
+__device__ __forceinline__ uint4 ld16(const uint4* p) {
+    if (NT) {
+        v4u t = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(p));
+        return make_uint4(t.x, t.y, t.z, t.w);
+    }
+    return *p;
+}
+template <bool NT>
+__device__ __forceinline__ void st16(uint4* p, uint4 v) {
+    if (NT) {
+        v4u t = {v.x, v.y, v.z, v.w};
+        __builtin_nontemporal_store(t, reinterpret_cast<v4u*>(p));
+    } else {
+        *p = v;
+    }
+}
+
+template <int D, int UNROLL, bool NT>
 __global__ __launch_bounds__(CMP_THREADS) void k_cmp_copy(CacheView src, const uint8_t* __restrict__ keep,
                                                           CacheViewMut dst, Shape sh, Workspace ws) {
     constexpr int VPR = D / 8;            // 16-byte vectors per row
     constexpr int RPI = 64 / VPR;         // rows moved by one wavefront instruction
-    constexpr int UNROLL = 4;
     __shared__ int wave_cnt[4];
     __shared__ int list[4][64];
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
@@ -136,8 +155,8 @@ __global__ __launch_bounds__(CMP_THREADS) void k_cmp_copy(CacheView src, const u
             const int r = r0 + u * RPI + sub;
             if (r < cnt) {
                 const int64_t se = (sbase + list[wave][r]) * VPR + col;
-                kk[u] = sk[se];
-                vv[u] = sv[se];
+                kk[u] = ld16<NT>(sk + se);
+                vv[u] = ld16<NT>(sv + se);
             }
         }
 #pragma unroll
@@ -145,8 +164,8 @@ __global__ __launch_bounds__(CMP_THREADS) void k_cmp_copy(CacheView src, const u
             const int r = r0 + u * RPI + sub;
             if (r < cnt) {
                 const int64_t de = (dbase + r) * VPR + col;
-                dk[de] = kk[u];
-                dv[de] = vv[u];
+                st16<NT>(dk + de, kk[u]);
+                st16<NT>(dv + de, vv[u]);
             }
         }
     }
@@ -157,12 +176,25 @@ kvtrim_status launch_compact(kvtrim_ctx* ctx, const CacheView& src, const uint8_
     const Shape& sh = ctx->shape;
     const Workspace& ws = ctx->ws;
     const int64_t max_chunks = src.cap / CMP_CHUNK + sh.nseg;
-    hipLaunchKernelGGL(k_cmp_scan, dim3(sh.nseg), dim3(CMP_THREADS), 0, st, src, keep, kept, dst, reserve, sh, ws);
+    { ProfScope prof(ctx, K_CMP_SCAN, st);
+      hipLaunchKernelGGL(k_cmp_scan, dim3(sh.nseg), dim3(CMP_THREADS), 0, st, src, keep, kept, dst, reserve, sh, ws); }
     if (max_chunks > 0) {
-        if (sh.head_dim == 128)
-            hipLaunchKernelGGL(k_cmp_copy<128>, dim3((unsigned)max_chunks), dim3(CMP_THREADS), 0, st, src, keep, dst, sh, ws);
-        else
-            hipLaunchKernelGGL(k_cmp_copy<64>, dim3((unsigned)max_chunks), dim3(CMP_THREADS), 0, st, src, keep, dst, sh, ws);
+        ProfScope prof(ctx, K_CMP_COPY, st);
+        const dim3 grid((unsigned)max_chunks), block(CMP_THREADS);
+#define KVTRIM_COPY(D_, U_, NT_) hipLaunchKernelGGL((k_cmp_copy<D_, U_, NT_>), grid, block, 0, st, src, keep, dst, sh, ws)
+#define KVTRIM_COPY_U(D_, NT_)                                       \
+    switch (ctx->cmp_unroll) {                                       \
+        case 1: KVTRIM_COPY(D_, 1, NT_); break;                      \
+        case 2: KVTRIM_COPY(D_, 2, NT_); break;                      \
+        default: KVTRIM_COPY(D_, 4, NT_); break;                     \
+    }
+        if (sh.head_dim == 128) {
+            if (ctx->cmp_nt) { KVTRIM_COPY_U(128, true) } else { KVTRIM_COPY_U(128, false) }
+        } else {
+            if (ctx->cmp_nt) { KVTRIM_COPY_U(64, true) } else { KVTRIM_COPY_U(64, false) }
+        }
+#undef KVTRIM_COPY_U
+#undef KVTRIM_COPY
     }
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;

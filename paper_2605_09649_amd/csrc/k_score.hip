@@ -24,6 +24,7 @@ kvtrim_status launch_score(kvtrim_ctx* ctx, const CacheView& c, const int32_t* n
     const Shape& sh = ctx->shape;
     int64_t bps = c.cap / ((int64_t)sh.nseg * 1024);
     bps = bps < 1 ? 1 : (bps > 64 ? 64 : bps);
+    ProfScope prof(ctx, K_SCORE, st);
     hipLaunchKernelGGL(k_score, dim3((unsigned)(sh.nseg * bps)), dim3(256), 0, st, c, now, score,
                        sh.segs_per_seq, (int)bps);
     KVTRIM_HIP(ctx, hipGetLastError());
@@ -65,6 +66,7 @@ __global__ __launch_bounds__(256) void k_append(CacheViewMut c, const uint16_t* 
 kvtrim_status launch_append(kvtrim_ctx* ctx, const CacheViewMut& c, const uint16_t* k_new, const uint16_t* v_new,
                             const float* lb_new, const int32_t* pos_new, int32_t n_new, hipStream_t st) {
     const Shape& sh = ctx->shape;
+    ProfScope prof(ctx, K_APPEND, st);
     hipLaunchKernelGGL(k_append, dim3(sh.nseg), dim3(256), 0, st, c, k_new, v_new, lb_new, pos_new, n_new,
                        sh.nseg, sh.head_dim, ctx->ws.err);
     KVTRIM_HIP(ctx, hipGetLastError());

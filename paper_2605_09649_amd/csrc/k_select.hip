@@ -11,15 +11,24 @@
 
 namespace kvtrim {
 
-constexpr int SEL_THREADS = 256;
+constexpr int SEL_THREADS = 256;      // mask / count kernels: one chunk per block, 8 entries per thread
 constexpr int CNT_THREADS = 1024;
+constexpr int HIST_THREADS = 1024;    // histogram passes: few fat blocks, so that few device-scope
+constexpr int HIST_BLOCKS = 256;      // atomics meet on one address when the LDS histograms are merged
+                                      // (the merged histogram is also kept in HIST_REPLICAS copies)
+constexpr int PLAN_ZERO_BLOCKS = 8;   // extra blocks of the plan kernel that clear the histograms
 
 __global__ __launch_bounds__(1024) void k_sel_plan(CacheView c, Shape sh, const int64_t* __restrict__ budget,
                                                    Workspace ws, int32_t* __restrict__ kept_out) {
     __shared__ int64_t lds64[17];
+    if (blockIdx.x > 0) {                      // clear the (replicated) histograms of the three passes
+        const int n = 3 * HIST_REPLICAS * sh.n_seq * RADIX_BINS;
+        for (int i = (blockIdx.x - 1) * blockDim.x + threadIdx.x; i < n; i += (gridDim.x - 1) * blockDim.x)
+            ws.hist[i] = 0;
+        return;
+    }
     build_chunk_table(c.seg_len, c.seg_start, sh.nseg, [](int) { return true; }, SEL_CHUNK, c.cap, ws.sel_chunk_prefix,
                       ws.sel_chunk_seg, ws.max_sel_chunks, ws.err, lds64);
-    for (int i = threadIdx.x; i < 3 * sh.n_seq * RADIX_BINS; i += blockDim.x) ws.hist[i] = 0;
     for (int i = threadIdx.x; i < 8; i += blockDim.x) ws.done[i] = 0;
     for (int g = threadIdx.x; g < sh.nseg; g += blockDim.x) kept_out[g] = 0;
     const bool empty = ws.sel_chunk_prefix[sh.nseg] == 0;   // also the state after a layout error
@@ -39,7 +48,7 @@ __global__ __launch_bounds__(1024) void k_sel_plan(CacheView c, Shape sh, const 
             st.rank = st.want;
             st.tie_quota = 0;
             st.keep_none = st.want == 0;
-            st.pad = 0;
+            st.need_rank = 0;
             ws.sel[seq] = st;
         }
     }
@@ -61,11 +70,12 @@ __device__ __forceinline__ bool digit_of(uint32_t key, uint32_t prefix, int* bin
 
 // Histogram of the next digit over the entries whose higher digits equal the prefix found so
 // far.  Blocks take contiguous ranges of chunks; the LDS histogram is flushed when the
-// sequence changes and at the end.
+// sequence changes and at the end.  Only one thread per block issues the device-scope fence
+// (a fence per wavefront costs an L2 write-back each and dominated the pass).
 template <int PASS>
-__global__ __launch_bounds__(SEL_THREADS) void k_sel_hist(CacheView c, const float* __restrict__ score,
-                                                          Shape sh, Workspace ws,
-                                                          uint32_t* __restrict__ thr_out) {
+__global__ __launch_bounds__(HIST_THREADS) void k_sel_hist(CacheView c, const float* __restrict__ score,
+                                                           Shape sh, Workspace ws,
+                                                           uint32_t* __restrict__ thr_out) {
     constexpr int NB = PASS == 2 ? 1024 : 2048;
     __shared__ uint32_t h[NB];
     __shared__ int64_t lds64[17];
@@ -74,9 +84,10 @@ __global__ __launch_bounds__(SEL_THREADS) void k_sel_hist(CacheView c, const flo
     const int total = ws.sel_chunk_prefix[sh.nseg];
     const int cpb = (total + gridDim.x - 1) / gridDim.x;
     const int c0 = min(total, (int)blockIdx.x * cpb), c1 = min(total, c0 + cpb);
-    uint32_t* hist = ws.hist + (size_t)PASS * sh.n_seq * RADIX_BINS;
+    uint32_t* hist_pass = ws.hist + (size_t)PASS * HIST_REPLICAS * sh.n_seq * RADIX_BINS;
+    uint32_t* hist = hist_pass + (size_t)(blockIdx.x % HIST_REPLICAS) * sh.n_seq * RADIX_BINS;
 
-    for (int i = tid; i < NB; i += SEL_THREADS) h[i] = 0;
+    for (int i = tid; i < NB; i += HIST_THREADS) h[i] = 0;
     __syncthreads();
     int cur_seq = -1;
     uint32_t prefix = 0;
@@ -87,7 +98,7 @@ __global__ __launch_bounds__(SEL_THREADS) void k_sel_hist(CacheView c, const flo
         if (seq != cur_seq) {
             if (cur_seq >= 0) {
                 __syncthreads();
-                for (int i = tid; i < NB; i += SEL_THREADS) {
+                for (int i = tid; i < NB; i += HIST_THREADS) {
                     uint32_t v = h[i];
                     if (v) atomicAdd(&hist[(size_t)cur_seq * RADIX_BINS + i], v);
                     h[i] = 0;
@@ -102,41 +113,48 @@ __global__ __launch_bounds__(SEL_THREADS) void k_sel_hist(CacheView c, const flo
         const int off = (ch - ws.sel_chunk_prefix[seg]) * SEL_CHUNK;
         const int end = min(c.seg_len[seg], off + SEL_CHUNK);
         const float* s = score + c.seg_start[seg];
-        for (int j = off + tid; j < end; j += SEL_THREADS) {
+        for (int j = off + tid; j < end; j += HIST_THREADS) {
             int bin;
             if (digit_of<PASS>(key_of_score(s[j]), prefix, &bin)) atomicAdd(&h[bin], 1u);
         }
     }
     __syncthreads();
     if (cur_seq >= 0) {
-        for (int i = tid; i < NB; i += SEL_THREADS) {
+        for (int i = tid; i < NB; i += HIST_THREADS) {
             uint32_t v = h[i];
             if (v) atomicAdd(&hist[(size_t)cur_seq * RADIX_BINS + i], v);
         }
     }
-    __threadfence();
     __syncthreads();
-    if (tid == 0) is_last = atomicAdd(&ws.done[PASS], 1u) == gridDim.x - 1;
+    if (tid == 0) {
+        __threadfence();
+        is_last = atomicAdd(&ws.done[PASS], 1u) == gridDim.x - 1;
+    }
     __syncthreads();
     if (!is_last) return;
     __threadfence();
 
     // Last block: per sequence, walk the histogram from the top bin down to the bin that
     // holds the entry of rank `rank` (1-based, in descending key order).
-    constexpr int PER = NB / SEL_THREADS;   // bins per thread, thread 0 owns the highest bins
+    constexpr int PER = NB / HIST_THREADS;   // bins per thread (1 or 2), thread 0 owns the highest bins
     for (int seq = 0; seq < sh.n_seq; ++seq) {
         SelState st = ws.sel[seq];
         if (st.keep_none) {
             if (PASS == 2 && tid == 0 && thr_out) thr_out[seq] = 0xFFFFFFFFu;
             continue;
         }
-        const uint32_t* hs = hist + (size_t)seq * RADIX_BINS;
         uint32_t cnt[PER];
         int64_t mine = 0;
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
-            cnt[i] = __hip_atomic_load(&hs[NB - 1 - (tid * PER + i)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            mine += cnt[i];
+            const int bin = NB - 1 - (tid * PER + i);
+            uint32_t v = 0;
+#pragma unroll
+            for (int r = 0; r < HIST_REPLICAS; ++r)
+                v += __hip_atomic_load(&hist_pass[((size_t)r * sh.n_seq + seq) * RADIX_BINS + bin], __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+            cnt[i] = v;
+            mine += v;
         }
         int64_t tot;
         int64_t above = block_excl_scan<int64_t>(mine, lds64, &tot);
@@ -151,6 +169,8 @@ __global__ __launch_bounds__(SEL_THREADS) void k_sel_hist(CacheView c, const flo
                     if (PASS == 2) {
                         st.thr_key = st.prefix;
                         st.tie_quota = st.rank;
+                        st.need_rank = st.rank < (int64_t)cnt[i];   // fewer survive than tie at the threshold
+                        if (st.need_rank) atomicOr((int*)&ws.done[4], 1);
                         if (thr_out) thr_out[seq] = st.thr_key;
                     }
                     ws.sel[seq] = st;
@@ -163,23 +183,25 @@ __global__ __launch_bounds__(SEL_THREADS) void k_sel_hist(CacheView c, const flo
     }
 }
 
-// Per chunk: entries above the threshold (added to the segment's kept count) and entries
-// equal to it.  The last block then turns the per-chunk tie counts into exclusive prefixes
-// per sequence and credits the ties that fit into the quota to their segments.
+// Only runs when, for some sequence, the entries equal to the threshold do not all fit.  Per
+// chunk of such a sequence: entries above the threshold (credited to the segment) and entries
+// equal to it; the last block then turns the per-chunk tie counts into exclusive prefixes per
+// sequence and credits the ties that fit into the quota to their segments.
 __global__ __launch_bounds__(CNT_THREADS) void k_sel_count(CacheView c, const float* __restrict__ score,
                                                            Shape sh, Workspace ws,
                                                            int32_t* __restrict__ kept_out) {
     __shared__ int64_t lds64[17];
     __shared__ int32_t lds32[17];
     __shared__ int is_last;
+    if (ws.done[4] == 0) return;                                  // uniform over the grid
     const int tid = threadIdx.x;
     const int total = ws.sel_chunk_prefix[sh.nseg];
     const int ch = blockIdx.x;
     if (ch < total) {
         const int seg = ws.sel_chunk_seg[ch];
         const SelState st = ws.sel[seg / sh.segs_per_seq];
-        int gt = 0, eq = 0;
-        if (!st.keep_none) {
+        if (st.need_rank) {
+            int gt = 0, eq = 0;
             const int off = (ch - ws.sel_chunk_prefix[seg]) * SEL_CHUNK;
             const int end = min(c.seg_len[seg], off + SEL_CHUNK);
             const float* s = score + c.seg_start[seg];
@@ -188,22 +210,25 @@ __global__ __launch_bounds__(CNT_THREADS) void k_sel_count(CacheView c, const fl
                 gt += key > st.thr_key;
                 eq += key == st.thr_key;
             }
-        }
-        gt = block_sum<int32_t>(gt, lds32);
-        eq = block_sum<int32_t>(eq, lds32);
-        if (tid == 0) {
-            if (gt) atomicAdd(&kept_out[seg], gt);
-            ws.chunk_eq[ch] = eq;
+            gt = block_sum<int32_t>(gt, lds32);
+            eq = block_sum<int32_t>(eq, lds32);
+            if (tid == 0) {
+                if (gt) atomicAdd(&kept_out[seg], gt);
+                ws.chunk_eq[ch] = eq;
+            }
         }
     }
-    __threadfence();
     __syncthreads();
-    if (tid == 0) is_last = atomicAdd(&ws.done[3], 1u) == gridDim.x - 1;
+    if (tid == 0) {
+        __threadfence();
+        is_last = atomicAdd(&ws.done[3], 1u) == gridDim.x - 1;
+    }
     __syncthreads();
     if (!is_last) return;
     __threadfence();
 
     for (int seq = 0; seq < sh.n_seq; ++seq) {
+        if (!ws.sel[seq].need_rank) continue;
         const int cb = ws.sel_chunk_prefix[seq * sh.segs_per_seq];
         const int ce = ws.sel_chunk_prefix[(seq + 1) * sh.segs_per_seq];
         const int64_t quota = ws.sel[seq].tie_quota;
@@ -227,9 +252,11 @@ __global__ __launch_bounds__(CNT_THREADS) void k_sel_count(CacheView c, const fl
 }
 
 // keep[e] = key > thr, or key == thr and the entry is among the first `quota` ties of its
-// sequence in storage order.
+// sequence in storage order.  When every tie fits (the usual case) the kernel also counts the
+// survivors of its chunk into kept_out; otherwise k_sel_count has done that.
 __global__ __launch_bounds__(SEL_THREADS) void k_sel_mask(CacheView c, const float* __restrict__ score,
-                                                          Shape sh, Workspace ws, uint8_t* __restrict__ keep) {
+                                                          Shape sh, Workspace ws, uint8_t* __restrict__ keep,
+                                                          int32_t* __restrict__ kept_out) {
     __shared__ int32_t lds32[17];
     const int tid = threadIdx.x;
     const int total = ws.sel_chunk_prefix[sh.nseg];
@@ -243,6 +270,17 @@ __global__ __launch_bounds__(SEL_THREADS) void k_sel_mask(CacheView c, const flo
     uint8_t* kp = keep + c.seg_start[seg];
     if (st.keep_none) {
         for (int j = off + tid; j < end; j += SEL_THREADS) kp[j] = 0;
+        return;
+    }
+    if (!st.need_rank) {                                          // every tie survives
+        int n = 0;
+        for (int j = off + tid; j < end; j += SEL_THREADS) {
+            const bool k = key_of_score(s[j]) >= st.thr_key;
+            kp[j] = k;
+            n += k;
+        }
+        n = block_sum<int32_t>(n, lds32);
+        if (tid == 0 && n) atomicAdd(&kept_out[seg], n);
         return;
     }
     const int64_t tb = ws.chunk_tie_base[ch];
@@ -278,13 +316,19 @@ kvtrim_status launch_select(kvtrim_ctx* ctx, const CacheView& c, const float* sc
     const Workspace& ws = ctx->ws;
     const int64_t max_chunks = c.cap / SEL_CHUNK + sh.nseg;      // bound on the chunk count
     const int n_chunk_blocks = (int)max_chunks;
-    const int hist_blocks = (int)(max_chunks < 1024 ? (max_chunks < 1 ? 1 : max_chunks) : 1024);
-    hipLaunchKernelGGL(k_sel_plan, dim3(1), dim3(1024), 0, st, c, sh, budget, ws, kept);
-    hipLaunchKernelGGL(k_sel_hist<0>, dim3(hist_blocks), dim3(SEL_THREADS), 0, st, c, score, sh, ws, thr);
-    hipLaunchKernelGGL(k_sel_hist<1>, dim3(hist_blocks), dim3(SEL_THREADS), 0, st, c, score, sh, ws, thr);
-    hipLaunchKernelGGL(k_sel_hist<2>, dim3(hist_blocks), dim3(SEL_THREADS), 0, st, c, score, sh, ws, thr);
-    hipLaunchKernelGGL(k_sel_count, dim3(n_chunk_blocks), dim3(CNT_THREADS), 0, st, c, score, sh, ws, kept);
-    hipLaunchKernelGGL(k_sel_mask, dim3(n_chunk_blocks), dim3(SEL_THREADS), 0, st, c, score, sh, ws, keep);
+    const int hist_blocks = (int)(max_chunks < HIST_BLOCKS ? (max_chunks < 1 ? 1 : max_chunks) : HIST_BLOCKS);
+    { ProfScope prof(ctx, K_SEL_PLAN, st);
+      hipLaunchKernelGGL(k_sel_plan, dim3(1 + PLAN_ZERO_BLOCKS), dim3(1024), 0, st, c, sh, budget, ws, kept); }
+    { ProfScope prof(ctx, K_SEL_HIST0, st);
+      hipLaunchKernelGGL(k_sel_hist<0>, dim3(hist_blocks), dim3(HIST_THREADS), 0, st, c, score, sh, ws, thr); }
+    { ProfScope prof(ctx, K_SEL_HIST1, st);
+      hipLaunchKernelGGL(k_sel_hist<1>, dim3(hist_blocks), dim3(HIST_THREADS), 0, st, c, score, sh, ws, thr); }
+    { ProfScope prof(ctx, K_SEL_HIST2, st);
+      hipLaunchKernelGGL(k_sel_hist<2>, dim3(hist_blocks), dim3(HIST_THREADS), 0, st, c, score, sh, ws, thr); }
+    { ProfScope prof(ctx, K_SEL_COUNT, st);
+      hipLaunchKernelGGL(k_sel_count, dim3(n_chunk_blocks), dim3(CNT_THREADS), 0, st, c, score, sh, ws, kept); }
+    { ProfScope prof(ctx, K_SEL_MASK, st);
+      hipLaunchKernelGGL(k_sel_mask, dim3(n_chunk_blocks), dim3(SEL_THREADS), 0, st, c, score, sh, ws, keep, kept); }
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;
 }

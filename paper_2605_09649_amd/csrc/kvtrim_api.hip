@@ -1,5 +1,6 @@
 // C ABI of libkvtrim: argument checks, workspace, and dispatch to the kernel launchers.
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <new>
@@ -57,7 +58,7 @@ static Layout layout_of(const kvtrim_config* c) {
     size_t cur = 0;
     l.off[0] = bump(cur, (nseg + 1) * sizeof(int32_t));                        // sel_chunk_prefix
     l.off[1] = bump(cur, l.max_sel_chunks * sizeof(int32_t));                  // sel_chunk_seg
-    l.off[2] = bump(cur, (size_t)3 * c->n_seq * RADIX_BINS * sizeof(uint32_t)); // hist
+    l.off[2] = bump(cur, (size_t)3 * HIST_REPLICAS * c->n_seq * RADIX_BINS * sizeof(uint32_t)); // hist
     l.off[3] = bump(cur, (size_t)c->n_seq * sizeof(SelState));                 // sel
     l.off[4] = bump(cur, 8 * sizeof(uint32_t));                                // done
     l.off[5] = bump(cur, l.max_sel_chunks * sizeof(int32_t));                  // chunk_eq
@@ -134,6 +135,15 @@ kvtrim_status kvtrim_create(kvtrim_ctx** out, const kvtrim_config* cfg) {
     sh.segs_per_seq = cfg->n_layers * cfg->n_kv_heads;
     sh.nseg = cfg->n_seq * sh.segs_per_seq;
     sh.group = cfg->n_q_heads / cfg->n_kv_heads;
+    ctx->att_chunk_min = 512;
+    if (const char* e = getenv("KVTRIM_ATT_CHUNK")) {            // tuning knob: rows per attention chunk
+        const int v = atoi(e);
+        if (v >= 256 && v <= 65536 && v % 64 == 0) ctx->att_chunk_min = v;
+    }
+    ctx->cmp_unroll = 4;
+    ctx->cmp_nt = 1;
+    if (const char* e = getenv("KVTRIM_CMP_UNROLL")) ctx->cmp_unroll = atoi(e);
+    if (const char* e = getenv("KVTRIM_CMP_NT")) ctx->cmp_nt = atoi(e) != 0;
     const Layout l = layout_of(cfg);
     ctx->ws_bytes = l.total;
     if (hipGetDevice(&ctx->device) != hipSuccess || hipMalloc(&ctx->ws_base, l.total) != hipSuccess) {
@@ -172,9 +182,69 @@ kvtrim_status kvtrim_create(kvtrim_ctx** out, const kvtrim_config* cfg) {
     return KVTRIM_OK;
 }
 
+static void free_profile(kvtrim_ctx* ctx) {
+    if (ctx->prof_ev) {
+        for (int i = 0; i < 2 * KVTRIM_PROFILE_MAX_LAUNCHES; ++i)
+            if (ctx->prof_ev[i]) (void)hipEventDestroy(ctx->prof_ev[i]);
+        delete[] ctx->prof_ev;
+        ctx->prof_ev = nullptr;
+    }
+    delete[] ctx->prof_kernel;
+    ctx->prof_kernel = nullptr;
+    ctx->prof_mask = 0;
+    ctx->prof_used = 0;
+}
+
+static const char* const kernel_names[KVTRIM_N_KERNELS] = {
+    "k_score", "k_sel_plan", "k_sel_hist<0>", "k_sel_hist<1>", "k_sel_hist<2>", "k_sel_count", "k_sel_mask",
+    "k_cmp_scan", "k_cmp_copy", "k_att_plan", "k_att_partial", "k_att_combine", "k_append"};
+
+const char* kvtrim_kernel_name(int32_t id) { return id >= 0 && id < KVTRIM_N_KERNELS ? kernel_names[id] : nullptr; }
+
+kvtrim_status kvtrim_profile_begin(kvtrim_ctx* ctx, uint32_t kernel_mask) {
+    if (!ctx) return KVTRIM_EINVAL;
+    if (!ctx->prof_ev) {
+        ctx->prof_ev = new (std::nothrow) hipEvent_t[2 * KVTRIM_PROFILE_MAX_LAUNCHES]();
+        ctx->prof_kernel = new (std::nothrow) int8_t[KVTRIM_PROFILE_MAX_LAUNCHES]();
+        if (!ctx->prof_ev || !ctx->prof_kernel) {
+            free_profile(ctx);
+            return KVTRIM_ENOMEM;
+        }
+        for (int i = 0; i < 2 * KVTRIM_PROFILE_MAX_LAUNCHES; ++i) {
+            hipError_t e = hipEventCreate(&ctx->prof_ev[i]);
+            if (e != hipSuccess) {
+                free_profile(ctx);
+                return hip_fail(ctx, e, "hipEventCreate");
+            }
+        }
+    }
+    ctx->prof_used = 0;
+    ctx->prof_mask = kernel_mask;
+    return KVTRIM_OK;
+}
+
+kvtrim_status kvtrim_profile_end(kvtrim_ctx* ctx, void* hip_stream, double* ms_sum, int64_t* launches) {
+    if (!ctx || !ms_sum || !launches) return KVTRIM_EINVAL;
+    ctx->prof_mask = 0;
+    for (int i = 0; i < KVTRIM_N_KERNELS; ++i) {
+        ms_sum[i] = 0.0;
+        launches[i] = 0;
+    }
+    KVTRIM_HIP(ctx, hipStreamSynchronize((hipStream_t)hip_stream));
+    for (int s = 0; s < ctx->prof_used; ++s) {
+        float ms = 0.f;
+        KVTRIM_HIP(ctx, hipEventElapsedTime(&ms, ctx->prof_ev[2 * s], ctx->prof_ev[2 * s + 1]));
+        ms_sum[ctx->prof_kernel[s]] += ms;
+        launches[ctx->prof_kernel[s]] += 1;
+    }
+    ctx->prof_used = 0;
+    return KVTRIM_OK;
+}
+
 kvtrim_status kvtrim_destroy(kvtrim_ctx* ctx) {
     if (!ctx) return KVTRIM_EINVAL;
     (void)hipDeviceSynchronize();
+    free_profile(ctx);
     if (ctx->err_host) (void)hipHostFree(ctx->err_host);
     if (ctx->ws_base) (void)hipFree(ctx->ws_base);
     delete ctx;

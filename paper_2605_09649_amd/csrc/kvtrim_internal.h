@@ -12,6 +12,7 @@ constexpr int SEL_CHUNK = 2048;      // selection: 256 threads x 8 entries
 constexpr int CMP_CHUNK = 256;       // compaction: 256 threads, 64 entries per wave
 constexpr int RADIX_BITS0 = 11, RADIX_BITS1 = 11, RADIX_BITS2 = 10;
 constexpr int RADIX_BINS = 2048;     // bins of the widest pass
+constexpr int HIST_REPLICAS = 8;     // copies of the merged histogram (spreads the device-scope atomics)
 
 constexpr int ERR_CAP = 1;           // bits of the sticky device flag
 constexpr int ERR_MISMATCH = 2;
@@ -51,14 +52,14 @@ struct SelState {
     int64_t rank;        // entries still to take inside the current bucket
     int64_t tie_quota;   // entries equal to thr_key to keep (in storage order)
     int32_t keep_none;   // want == 0
-    int32_t pad;
+    int32_t need_rank;   // only some of the entries equal to thr_key fit: they must be ranked in order
 };
 
 struct Workspace {
     // selection
     int32_t* sel_chunk_prefix;   // [nseg+1] first chunk of each segment
     int32_t* sel_chunk_seg;      // [max_sel_chunks] segment of each chunk
-    uint32_t* hist;              // [3][n_seq][RADIX_BINS]
+    uint32_t* hist;              // [3][HIST_REPLICAS][n_seq][RADIX_BINS]
     SelState* sel;               // [n_seq]
     uint32_t* done;              // [8] "last block" counters
     int32_t* chunk_eq;           // [max_sel_chunks] entries equal to the threshold
@@ -77,6 +78,14 @@ struct Workspace {
 
 }  // namespace kvtrim
 
+namespace kvtrim {
+enum KernelId {
+    K_SCORE = 0, K_SEL_PLAN, K_SEL_HIST0, K_SEL_HIST1, K_SEL_HIST2, K_SEL_COUNT, K_SEL_MASK,
+    K_CMP_SCAN, K_CMP_COPY, K_ATT_PLAN, K_ATT_PARTIAL, K_ATT_COMBINE, K_APPEND, K_COUNT
+};
+static_assert(K_COUNT == KVTRIM_N_KERNELS, "kernel table out of step with the header");
+}  // namespace kvtrim
+
 struct kvtrim_ctx {
     kvtrim_config cfg;
     kvtrim::Shape shape;
@@ -85,7 +94,14 @@ struct kvtrim_ctx {
     size_t ws_bytes;
     int32_t* err_host;           // pinned mirror of the device flag
     int device;
+    int att_chunk_min;           // rows per attention chunk (multiple of 64, >= 256); KVTRIM_ATT_CHUNK overrides
+    int cmp_unroll, cmp_nt;      // row-copy shape of the compaction (KVTRIM_CMP_UNROLL, KVTRIM_CMP_NT override)
     char last_error[256];
+    // instrumentation
+    uint32_t prof_mask;
+    hipEvent_t* prof_ev;         // [2 * KVTRIM_PROFILE_MAX_LAUNCHES] start/stop pairs
+    int8_t* prof_kernel;         // kernel id of each bracketed launch
+    int prof_used;
 };
 
 namespace kvtrim {
@@ -110,6 +126,25 @@ kvtrim_status hip_fail(kvtrim_ctx* ctx, hipError_t e, const char* what);
         hipError_t _e = (expr);                                        \
         if (_e != hipSuccess) return ::kvtrim::hip_fail(ctx, _e, #expr); \
     } while (0)
+
+// Brackets the launches made while it is alive with a pair of events when profiling asks for it.
+struct ProfScope {
+    kvtrim_ctx* ctx;
+    hipStream_t st;
+    int slot;
+    ProfScope(kvtrim_ctx* c, int kernel, hipStream_t s) : ctx(c), st(s), slot(-1) {
+        if ((c->prof_mask >> kernel) & 1u) {
+            if (c->prof_used < KVTRIM_PROFILE_MAX_LAUNCHES) {
+                slot = c->prof_used++;
+                c->prof_kernel[slot] = (int8_t)kernel;
+                (void)hipEventRecord(c->prof_ev[2 * slot], st);
+            }
+        }
+    }
+    ~ProfScope() {
+        if (slot >= 0) (void)hipEventRecord(ctx->prof_ev[2 * slot + 1], st);
+    }
+};
 
 // ---- device helpers --------------------------------------------------------------------
 __device__ __forceinline__ uint32_t key_of_score(float s) {
