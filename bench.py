@@ -20,9 +20,9 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
-# HBM bytes per launch of the dominant kernel (k_cmp_copy) from rocprofv3 --pmc FETCH_SIZE /
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs, scaled by a plain copy kernel; None until measured for this workload.
-MEASURED_TRAFFIC = {"long": None, "llama": None}
+MEASURED_TRAFFIC = {("long", "k_cmp_attn"): None, ("long", "k_cmp_copy"): None}
 
 
 def log(*a):
@@ -51,6 +51,8 @@ def main():
     ap.add_argument("--workload", default="long", choices=["long", "llama", "vlm", "tiny"])
     ap.add_argument("--prefill", type=int, default=None, help="override the prefilled length (scaled-down run)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--unfused", action="store_true",
+                    help="run stages 3 and 4 as two calls (kvtrim_compact, kvtrim_decode_attn) instead of the fused one")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -110,8 +112,11 @@ def main():
         kv.kvtrim_score(ctx, cur, nows[s], score)
         kv.kvtrim_select_global(ctx, cur, score, budget, keep, kept, thr)
         dst = spare[state["flip"]]
-        kv.kvtrim_compact(ctx, cur, keep, kept, dst, reserve)
-        kv.kvtrim_decode_attn(ctx, dst, inp["q"], 0, w.n_layers, scale, out, lse)
+        if args.unfused:
+            kv.kvtrim_compact(ctx, cur, keep, kept, dst, reserve)
+            kv.kvtrim_decode_attn(ctx, dst, inp["q"], 0, w.n_layers, scale, out, lse)
+        else:
+            kv.kvtrim_compact_attn(ctx, cur, keep, kept, dst, reserve, inp["q"], 0, w.n_layers, scale, out, lse)
         state["src"] = dst
         state["flip"] ^= 1
 
@@ -133,7 +138,7 @@ def main():
     log(f"[bench] first step (prefill -> budget): {first_ms:.3f} ms; steady state: {n_cand} candidates, {n_ret} retained")
 
     # ---- timed region: exactly K steps; the dominant kernels are bracketed by HIP events on the launch stream
-    mask = (1 << 8) | (1 << 10)               # k_cmp_copy, k_att_partial
+    mask = (1 << 8) | (1 << 10) | (1 << 13)   # k_cmp_copy, k_att_partial, k_cmp_attn
     kv.kvtrim_profile_begin(ctx, mask)
     torch.cuda.synchronize()
     t_begin = time.perf_counter()
@@ -146,12 +151,21 @@ def main():
     ms_per_step = (t_end - t_begin) * 1e3 / K
     alg = algorithmic_bytes(w, n_cand, n_ret)
     alg_total = sum(alg.values())
-    copy_ms, copy_n = prof["k_cmp_copy"]
-    att_ms, att_n = prof["k_att_partial"]
-    copy_avg_ms = copy_ms / copy_n
-    achieved = alg["compact"] / (copy_avg_ms * 1e-3) / 1e9
-    log(f"[bench] {ms_per_step:.4f} ms/step; k_cmp_copy {copy_avg_ms:.4f} ms ({achieved:.0f} GB/s algorithmic); "
-        f"k_att_partial {att_ms / att_n:.4f} ms ({alg['attend'] / (att_ms / att_n * 1e-3) / 1e9:.0f} GB/s)")
+    if args.unfused:
+        dom, dom_bytes = "k_cmp_copy", alg["compact"]
+    else:                                      # the fused kernel does the work of stages 3 and 4
+        dom, dom_bytes = "k_cmp_attn", alg["compact"] + alg["attend"]
+    dom_ms, dom_n = prof[dom]
+    dom_avg_ms = dom_ms / dom_n
+    achieved = dom_bytes / (dom_avg_ms * 1e-3) / 1e9
+    log(f"[bench] {ms_per_step:.4f} ms/step ({alg_total / (ms_per_step * 1e-3) / 1e9:.0f} GB/s algorithmic end to end); "
+        f"{dom} {dom_avg_ms:.4f} ms ({achieved:.0f} GB/s algorithmic)")
+    second = None
+    if args.unfused:
+        att_ms, att_n = prof["k_att_partial"]
+        second = {"kernel": "k_att_partial", "avg_launch_ms": att_ms / att_n,
+                  "achieved": alg["attend"] / (att_ms / att_n * 1e-3) / 1e9}
+        log(f"[bench] k_att_partial {att_ms / att_n:.4f} ms ({second['achieved']:.0f} GB/s)")
 
     result = {
         "metric": "eviction+decode steps/sec and achieved HBM GB/s (% of peak), 32Lx8H 128K ctx",
@@ -169,17 +183,17 @@ def main():
         "config": {
             "workload": f"{w.name}: S{w.n_seq} L{w.n_layers} Hkv{w.n_kv_heads} Hq{w.n_q_heads} D{w.head_dim}, "
                         f"{w.prefill[0]} prefilled, B={B} ({n_cand} candidates/step, {n_ret} retained)",
-            "stages": "append+score+select_global+compact+decode_attn, four C-ABI calls per step, no graph capture",
+            "stages": ("append, score, select_global, compact, decode_attn (five C-ABI calls per step)" if args.unfused else
+                       "append, score, select_global, compact_attn (stages 3+4 fused; four C-ABI calls per step)"),
             "first_step_ms": first_ms,
         },
         "end_to_end": {"algorithmic_bytes_per_step": alg_total, "achieved_GBps": alg_total / (ms_per_step * 1e-3) / 1e9,
                        "frac_of_hbm_peak": alg_total / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
                        "bytes_by_stage": alg},
-        "roofline": {"bound": "hbm", "kernel": "k_cmp_copy", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(w.name),
-                     "avg_launch_ms": copy_avg_ms, "launches": copy_n,
-                     "second_kernel": {"kernel": "k_att_partial", "avg_launch_ms": att_ms / att_n,
-                                       "achieved": alg["attend"] / (att_ms / att_n * 1e-3) / 1e9}},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get((w.name, dom)),
+                     "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_avg_ms, "launches": dom_n,
+                     "second_kernel": second},
     }
 
     # ---- CPU baseline: the oracle replays ONE more step of the same workload on the host cores, and the

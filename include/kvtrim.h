@@ -139,6 +139,16 @@ kvtrim_status kvtrim_decode_attn(kvtrim_ctx *ctx, const kvtrim_cache *c, const v
                                  int32_t layer_begin, int32_t layer_end, float softmax_scale,
                                  float *out, float *lse, void *hip_stream);
 
+/* Stages 3 + 4 fused: exactly kvtrim_compact(src -> dst) followed by
+ * kvtrim_decode_attn(dst), with the same arguments, results and device-side errors,
+ * but every surviving K/V row is read from HBM once: it is used for the attention of
+ * its segment while it is moved.  (When the source cache is too large for the
+ * partial-result buffer of the context the two stages simply run one after the other.) */
+kvtrim_status kvtrim_compact_attn(kvtrim_ctx *ctx, const kvtrim_cache *src, const uint8_t *keep,
+                                  const int32_t *kept, kvtrim_cache *dst, int32_t reserve, const void *q,
+                                  int32_t layer_begin, int32_t layer_end, float softmax_scale, float *out,
+                                  float *lse, void *hip_stream);
+
 /* Support - new tokens enter the cache (Sec. 3.2: beta is fixed when the token is
  * first cached).  Appends n_new entries to every segment, in order, behind its
  * current end and adds n_new to seg_len.  k_new, v_new: device bf16
@@ -159,7 +169,7 @@ kvtrim_status kvtrim_append(kvtrim_ctx *ctx, kvtrim_cache *c, const void *k_new,
  * end waits for `hip_stream` and writes, per kernel id, the summed duration in
  * milliseconds and the number of bracketed launches into host arrays of
  * KVTRIM_N_KERNELS elements.  Do not capture a HIP graph while profiling is on. */
-#define KVTRIM_N_KERNELS 13
+#define KVTRIM_N_KERNELS 14
 #define KVTRIM_PROFILE_MAX_LAUNCHES 4096
 kvtrim_status kvtrim_profile_begin(kvtrim_ctx *ctx, uint32_t kernel_mask);
 kvtrim_status kvtrim_profile_end(kvtrim_ctx *ctx, void *hip_stream, double *ms_sum_host,

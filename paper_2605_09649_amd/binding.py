@@ -13,9 +13,9 @@ STATUS = {0: "KVTRIM_OK", -1: "KVTRIM_EINVAL", -2: "KVTRIM_ENOMEM", -3: "KVTRIM_
 
 EXPORTS = ["kvtrim_create", "kvtrim_destroy", "kvtrim_workspace_bytes", "kvtrim_last_error",
            "kvtrim_poll_error", "kvtrim_score", "kvtrim_select_global", "kvtrim_compact",
-           "kvtrim_decode_attn", "kvtrim_append", "kvtrim_profile_begin", "kvtrim_profile_end",
+           "kvtrim_decode_attn", "kvtrim_compact_attn", "kvtrim_append", "kvtrim_profile_begin", "kvtrim_profile_end",
            "kvtrim_kernel_name"]
-N_KERNELS = 13
+N_KERNELS = 14
 
 
 class KvtrimError(RuntimeError):
@@ -59,6 +59,9 @@ def load_library():
                                        C.c_int32, C.c_void_p]
         lib.kvtrim_decode_attn.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_int32, C.c_int32,
                                            C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.kvtrim_compact_attn.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.POINTER(_Cache),
+                                            C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p,
+                                            C.c_void_p, C.c_void_p]
         lib.kvtrim_append.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_int32, C.c_void_p]
         lib.kvtrim_profile_begin.argtypes = [C.c_void_p, C.c_uint32]
@@ -187,6 +190,14 @@ def kvtrim_decode_attn(ctx, cache, q, layer_begin, layer_end, softmax_scale, out
                                                   int(layer_begin), int(layer_end), float(softmax_scale),
                                                   _ptr(out, torch.float32), _ptr(lse, torch.float32),
                                                   _stream(stream)), "kvtrim_decode_attn")
+
+
+def kvtrim_compact_attn(ctx, src, keep, kept, dst, reserve, q, layer_begin, layer_end, softmax_scale, out, lse=None,
+                        stream=None):
+    _check(ctx, load_library().kvtrim_compact_attn(
+        ctx.handle, C.byref(src.c), _ptr(keep, torch.uint8), _ptr(kept, torch.int32), C.byref(dst.c), int(reserve),
+        _ptr(q, torch.bfloat16), int(layer_begin), int(layer_end), float(softmax_scale), _ptr(out, torch.float32),
+        _ptr(lse, torch.float32), _stream(stream)), "kvtrim_compact_attn")
 
 
 def kvtrim_append(ctx, cache, k_new, v_new, log_beta_new, pos_new, n_new, stream=None):

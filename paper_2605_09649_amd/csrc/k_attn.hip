@@ -24,14 +24,13 @@ typedef __attribute__((ext_vector_type(4))) short short4v;
 
 __global__ __launch_bounds__(1024) void k_att_plan(CacheView c, Shape sh, Workspace ws, int chunk,
                                                    int layer_begin, int layer_end, int64_t max_chunks) {
-    __shared__ int64_t lds64[17];
     const int H = sh.n_kv_heads, L = sh.n_layers;
     auto in_range = [=](int g) {
         const int layer = (g / H) % L;
         return layer >= layer_begin && layer < layer_end;
     };
     build_chunk_table(c.seg_len, c.seg_start, sh.nseg, in_range, chunk, c.cap, ws.att_chunk_prefix,
-                      ws.att_chunk_seg, max_chunks, ws.err, lds64);
+                      ws.att_desc, max_chunks, nullptr, ws.err);
 }
 
 // broadcast lane `Q` of every 16-lane row to the whole row
@@ -108,11 +107,10 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
     const int total = ws.att_chunk_prefix[sh.nseg];
     const int ch = blockIdx.x;
     if (ch >= total) return;
-    const int seg = ws.att_chunk_seg[ch];
-    const int off = (ch - ws.att_chunk_prefix[seg]) * chunk;
-    const int len = c.seg_len[seg];
-    const int row_end = min(len, off + chunk);                    // rows [off, row_end) of the segment
-    const int64_t base = c.seg_start[seg];
+    const ChunkDesc cd = ws.att_desc[ch];
+    const int seg = cd.seg;
+    const int off = 0, row_end = cd.n;                            // rows [0, n) counted from cd.first
+    const int64_t base = cd.first;
     const int c16 = lane & 15, b4 = lane >> 4;
 
     // query fragments: lane (query c16, k-group b4), MFMA step j covers elements (4j + b4)*E ..
@@ -235,9 +233,10 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
 // a tile are independent of each other and can all be in flight).
 constexpr int COMB_TILE = 16;
 template <int D>
-__global__ __launch_bounds__(ATT_THREADS) void k_att_combine(Shape sh, Workspace ws, int layer_begin,
-                                                             int layer_end, float* __restrict__ out,
-                                                             float* __restrict__ lse) {
+__global__ __launch_bounds__(ATT_THREADS) void k_att_combine(Shape sh, Workspace ws,
+                                                             const int32_t* __restrict__ chunk_prefix,
+                                                             int layer_begin, int layer_end,
+                                                             float* __restrict__ out, float* __restrict__ lse) {
     __shared__ float s_m[COMB_TILE][8], s_l[COMB_TILE][8];
     const int G = sh.group;
     const int nl = layer_end - layer_begin;
@@ -245,7 +244,9 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_combine(Shape sh, Workspace
     const int seq = blockIdx.x / per, r = blockIdx.x % per;
     const int layer = layer_begin + r / sh.n_kv_heads, head = r % sh.n_kv_heads;
     const int seg = (seq * sh.n_layers + layer) * sh.n_kv_heads + head;
-    const int c0 = ws.att_chunk_prefix[seg], c1 = ws.att_chunk_prefix[seg + 1];
+    if (__hip_atomic_load(ws.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;   // tables may be stale
+    const int c0 = chunk_prefix[seg];
+    const int c1 = min(chunk_prefix[seg + 1], (int)ws.max_att_chunks);
     const int64_t hq0 = ((int64_t)seq * sh.n_layers + layer) * sh.n_q_heads + (int64_t)head * G;
     const float LN2 = 0.6931471805599453f;
     constexpr int PAIRS = (8 * D + ATT_THREADS - 1) / ATT_THREADS;   // (query, d) pairs per thread, G <= 8
@@ -342,12 +343,21 @@ kvtrim_status launch_attn(kvtrim_ctx* ctx, const CacheView& c, const uint16_t* q
                   : dispatch_partial<64>(sh.group, c, q, sh, ws, chunk, scale_log2, (unsigned)max_chunks, st);
     }
     if (!ok) return KVTRIM_EINVAL;
+    return launch_combine(ctx, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, st);
+}
+
+// Merges the per-chunk partial results in ws.att_partial; chunk_prefix[g] .. chunk_prefix[g+1]
+// are the chunks of segment g.
+kvtrim_status launch_combine(kvtrim_ctx* ctx, const int32_t* chunk_prefix, int32_t layer_begin,
+                             int32_t layer_end, float* out, float* lse, hipStream_t st) {
+    const Shape& sh = ctx->shape;
+    const Workspace& ws = ctx->ws;
     const unsigned nblk = (unsigned)(sh.n_seq * (layer_end - layer_begin) * sh.n_kv_heads);
     ProfScope prof(ctx, K_ATT_COMBINE, st);
     if (sh.head_dim == 128)
-        hipLaunchKernelGGL(k_att_combine<128>, dim3(nblk), dim3(ATT_THREADS), 0, st, sh, ws, layer_begin, layer_end, out, lse);
+        hipLaunchKernelGGL(k_att_combine<128>, dim3(nblk), dim3(ATT_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse);
     else
-        hipLaunchKernelGGL(k_att_combine<64>, dim3(nblk), dim3(ATT_THREADS), 0, st, sh, ws, layer_begin, layer_end, out, lse);
+        hipLaunchKernelGGL(k_att_combine<64>, dim3(nblk), dim3(ATT_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse);
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;
 }

@@ -69,7 +69,11 @@ __global__ __launch_bounds__(CMP_THREADS) void k_cmp_scan(CacheView src, const u
         }
         if (lane == 0) {
             ws.cmp_chunk_dst[cbase + ch] = cnt;
-            ws.cmp_chunk_seg[cbase + ch] = g;
+            ChunkDesc d;
+            d.first = src.seg_start[g] + (int64_t)ch * CMP_CHUNK;
+            d.n = min(CMP_CHUNK, len - ch * CMP_CHUNK);
+            d.seg = g;
+            ws.cmp_desc[cbase + ch] = d;
         }
     }
     __syncthreads();
@@ -124,12 +128,9 @@ __global__ __launch_bounds__(CMP_THREADS) void k_cmp_copy(CacheView src, const u
     const int total = ws.cmp_chunk_prefix[sh.nseg];
     const int ch = blockIdx.x;
     if (ch >= total) return;
-    const int seg = ws.cmp_chunk_seg[ch];
-    const int off = (ch - ws.cmp_chunk_prefix[seg]) * CMP_CHUNK;
-    const int len = src.seg_len[seg];
-    const int64_t sbase = src.seg_start[seg] + off;               // first source entry of the chunk
-    const int j = off + tid;
-    const bool flag = j < len && keep[sbase + tid] != 0;
+    const ChunkDesc d = ws.cmp_desc[ch];
+    const int64_t sbase = d.first;                                // first source entry of the chunk
+    const bool flag = tid < d.n && keep[sbase + tid] != 0;
     const uint64_t mask = __ballot(flag);
     const int rank = mbcnt(mask);
     const int cnt = __popcll(mask);
@@ -171,13 +172,19 @@ __global__ __launch_bounds__(CMP_THREADS) void k_cmp_copy(CacheView src, const u
     }
 }
 
+void launch_cmp_scan(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const int32_t* kept,
+                     const CacheViewMut& dst, int32_t reserve, hipStream_t st) {
+    ProfScope prof(ctx, K_CMP_SCAN, st);
+    hipLaunchKernelGGL(k_cmp_scan, dim3(ctx->shape.nseg), dim3(CMP_THREADS), 0, st, src, keep, kept, dst, reserve,
+                       ctx->shape, ctx->ws);
+}
+
 kvtrim_status launch_compact(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const int32_t* kept,
                              const CacheViewMut& dst, int32_t reserve, hipStream_t st) {
     const Shape& sh = ctx->shape;
     const Workspace& ws = ctx->ws;
     const int64_t max_chunks = src.cap / CMP_CHUNK + sh.nseg;
-    { ProfScope prof(ctx, K_CMP_SCAN, st);
-      hipLaunchKernelGGL(k_cmp_scan, dim3(sh.nseg), dim3(CMP_THREADS), 0, st, src, keep, kept, dst, reserve, sh, ws); }
+    launch_cmp_scan(ctx, src, keep, kept, dst, reserve, st);
     if (max_chunks > 0) {
         ProfScope prof(ctx, K_CMP_COPY, st);
         const dim3 grid((unsigned)max_chunks), block(CMP_THREADS);

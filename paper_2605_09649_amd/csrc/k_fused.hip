@@ -1,0 +1,290 @@
+// Stages 3 + 4 in one pass over the retained rows: while a surviving K/V row travels from
+// the source cache to its slot in the compacted cache it is also used for the decode
+// attention of its segment (Sec. 2.1, Eq. reform with r in {0,1}), so K and V are read from
+// HBM once per step instead of twice.  Result is the same as compaction followed by
+// attention over the compacted cache.
+//
+// One block per 256-entry chunk of a source segment (the chunk table and the destination
+// offsets come from k_cmp_scan).  A wavefront ranks the survivors of its 64 entries with a
+// ballot, then moves them four rows per instruction (16 lanes x 16 bytes = one 256-byte row,
+// so loads and stores are whole rows).  In that layout a lane owns the same 8-element column
+// slice of the K row and of the V row:
+//   q.k   8 FMAs per query head and lane, then a 16-lane all-reduce with DPP
+//   p.v   8 FMAs per query head and lane, no cross-lane traffic
+// Each 16-lane row group keeps its own online-softmax state; the four row groups of a
+// wavefront are merged with lane shuffles, the four wavefronts through LDS, and the chunks
+// of a segment by k_att_combine.
+#include "kvtrim_device.h"
+
+namespace kvtrim {
+
+constexpr int FUS_THREADS = 256;
+static_assert(CMP_CHUNK == FUS_THREADS, "one thread per entry of a chunk");
+
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+typedef unsigned v2u __attribute__((ext_vector_type(2)));
+
+template <int D>
+struct Row;
+template <>
+struct Row<128> {
+    typedef uint4 vec;
+    static constexpr int E = 8;
+    static __device__ __forceinline__ vec ld(const vec* p) {
+        v4u t = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(p));
+        return make_uint4(t.x, t.y, t.z, t.w);
+    }
+    static __device__ __forceinline__ void st(vec* p, vec v) {
+        v4u t = {v.x, v.y, v.z, v.w};
+        __builtin_nontemporal_store(t, reinterpret_cast<v4u*>(p));
+    }
+    static __device__ __forceinline__ void unpack(vec x, float* f) {
+        f[0] = __uint_as_float(x.x << 16); f[1] = __uint_as_float(x.x & 0xffff0000u);
+        f[2] = __uint_as_float(x.y << 16); f[3] = __uint_as_float(x.y & 0xffff0000u);
+        f[4] = __uint_as_float(x.z << 16); f[5] = __uint_as_float(x.z & 0xffff0000u);
+        f[6] = __uint_as_float(x.w << 16); f[7] = __uint_as_float(x.w & 0xffff0000u);
+    }
+};
+template <>
+struct Row<64> {
+    typedef uint2 vec;
+    static constexpr int E = 4;
+    static __device__ __forceinline__ vec ld(const vec* p) {
+        v2u t = __builtin_nontemporal_load(reinterpret_cast<const v2u*>(p));
+        return make_uint2(t.x, t.y);
+    }
+    static __device__ __forceinline__ void st(vec* p, vec v) {
+        v2u t = {v.x, v.y};
+        __builtin_nontemporal_store(t, reinterpret_cast<v2u*>(p));
+    }
+    static __device__ __forceinline__ void unpack(vec x, float* f) {
+        f[0] = __uint_as_float(x.x << 16); f[1] = __uint_as_float(x.x & 0xffff0000u);
+        f[2] = __uint_as_float(x.y << 16); f[3] = __uint_as_float(x.y & 0xffff0000u);
+    }
+};
+
+// sum over the 16 lanes of a row group, result in every lane
+__device__ __forceinline__ float row16_sum(float x) {
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x141, 0xF, 0xF, false));  // row_half_mirror
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x140, 0xF, 0xF, false));  // row_mirror
+    return x;
+}
+
+template <int D, int G>
+__global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const uint8_t* __restrict__ keep,
+                                                          CacheViewMut dst, const uint16_t* __restrict__ q,
+                                                          Shape sh, Workspace ws, float scale_log2,
+                                                          int layer_begin, int layer_end) {
+    typedef Row<D> R;
+    typedef typename R::vec vec;
+    constexpr int E = R::E;
+    constexpr int VPR = 16;                                       // lanes (vectors) per row
+    constexpr int NW = FUS_THREADS / 64;
+    __shared__ int wave_cnt[NW];
+    __shared__ int list[NW][64];
+    __shared__ float s_m[NW][G], s_l[NW][G];
+    __shared__ float s_o[NW][G][D];
+
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    if (__hip_atomic_load(ws.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
+    const int total = ws.cmp_chunk_prefix[sh.nseg];
+    const int ch = blockIdx.x;
+    if (ch >= total) return;
+    const ChunkDesc cd = ws.cmp_desc[ch];
+    const int64_t sbase = cd.first;
+    const bool flag = tid < cd.n && keep[sbase + tid] != 0;
+    const uint64_t mask = __ballot(flag);
+    const int rank = mbcnt(mask);
+    const int cnt = __popcll(mask);
+    if (lane == 0) wave_cnt[wave] = cnt;
+    if (flag) list[wave][rank] = tid;
+    __syncthreads();
+    int wbase = 0;
+    for (int w = 0; w < wave; ++w) wbase += wave_cnt[w];
+    const int64_t dbase = ws.cmp_chunk_dst[ch] + wbase;
+    if (flag) {
+        dst.log_beta[dbase + rank] = src.log_beta[sbase + tid];
+        dst.pos[dbase + rank] = src.pos[sbase + tid];
+    }
+
+    const int seg = cd.seg;
+    const int seq = seg / sh.segs_per_seq, lh = seg % sh.segs_per_seq;
+    const int layer = lh / sh.n_kv_heads, head = lh % sh.n_kv_heads;
+    const bool attend = layer >= layer_begin && layer < layer_end;   // uniform over the block
+    const int sub = lane >> 4, col = lane & 15;
+
+    float qf[G][E];
+    if (attend) {
+        const int64_t hq0 = ((int64_t)seq * sh.n_layers + layer) * sh.n_q_heads + (int64_t)head * G;
+#pragma unroll
+        for (int g = 0; g < G; ++g) R::unpack(reinterpret_cast<const vec*>(q + (hq0 + g) * D)[col], qf[g]);
+    }
+    float o[G][E], m[G], l[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        m[g] = -INFINITY;
+        l[g] = 0.f;
+#pragma unroll
+        for (int e = 0; e < E; ++e) o[g][e] = 0.f;
+    }
+
+    const vec* sk = reinterpret_cast<const vec*>(src.k);
+    const vec* sv = reinterpret_cast<const vec*>(src.v);
+    vec* dk = reinterpret_cast<vec*>(dst.k);
+    vec* dv = reinterpret_cast<vec*>(dst.v);
+
+    for (int r0 = 0; r0 < cnt; r0 += 16) {                        // 16 rows per softmax update
+        vec kk[4], vv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int r = min(r0 + u * 4 + sub, cnt - 1);         // clamped: loads stay on live rows
+            const int64_t se = (sbase + list[wave][r]) * VPR + col;
+            kk[u] = R::ld(sk + se);
+            vv[u] = R::ld(sv + se);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int r = r0 + u * 4 + sub;
+            if (r < cnt) {
+                const int64_t de = (dbase + r) * VPR + col;
+                R::st(dk + de, kk[u]);
+                R::st(dv + de, vv[u]);
+            }
+        }
+        if (!attend) continue;
+        float z[4][G];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float kf[E];
+            R::unpack(kk[u], kf);
+            const bool valid = r0 + u * 4 + sub < cnt;
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                float part = 0.f;
+#pragma unroll
+                for (int e = 0; e < E; ++e) part = fmaf(qf[g][e], kf[e], part);
+                const float s = row16_sum(part);
+                z[u][g] = valid ? s * scale_log2 : -INFINITY;
+            }
+        }
+        float vf[4][E];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) R::unpack(vv[u], vf[u]);
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const float tmax = fmaxf(fmaxf(z[0][g], z[1][g]), fmaxf(z[2][g], z[3][g]));
+            const float m_new = fmaxf(m[g], tmax);
+            const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f(m[g] - m_safe);
+            float p[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) p[u] = __builtin_amdgcn_exp2f(z[u][g] - m_safe);
+            l[g] = l[g] * alpha + ((p[0] + p[1]) + (p[2] + p[3]));
+            m[g] = m_new;
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                float acc = o[g][e] * alpha;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) acc = fmaf(p[u], vf[u][e], acc);
+                o[g][e] = acc;
+            }
+        }
+    }
+    if (!attend) return;
+
+    // merge the four row groups of the wavefront, then the wavefronts of the block
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        float m_all = fmaxf(m[g], __shfl_xor(m[g], 16, 64));
+        m_all = fmaxf(m_all, __shfl_xor(m_all, 32, 64));
+        const float m_fin = m_all == -INFINITY ? 0.f : m_all;
+        const float wgt = __builtin_amdgcn_exp2f(m[g] - m_fin);
+        float l_all = l[g] * wgt;
+        l_all += __shfl_xor(l_all, 16, 64);
+        l_all += __shfl_xor(l_all, 32, 64);
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            float x = o[g][e] * wgt;
+            x += __shfl_xor(x, 16, 64);
+            x += __shfl_xor(x, 32, 64);
+            o[g][e] = x;
+        }
+        if (lane == 0) {
+            s_m[wave][g] = m_all;
+            s_l[wave][g] = l_all;
+        }
+    }
+    if (sub == 0) {
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int e = 0; e < E; ++e) s_o[wave][g][col * E + e] = o[g][e];
+    }
+    __syncthreads();
+    float* part = ws.att_partial + (size_t)ch * G * (D + 2);
+    for (int idx = tid; idx < G * D; idx += FUS_THREADS) {
+        const int g = idx / D, d = idx % D;
+        float M = -INFINITY;
+#pragma unroll
+        for (int s = 0; s < NW; ++s) M = fmaxf(M, s_m[s][g]);
+        const float Ms = M == -INFINITY ? 0.f : M;
+        float accd = 0.f, lsum = 0.f;
+#pragma unroll
+        for (int s = 0; s < NW; ++s) {
+            const float w = __builtin_amdgcn_exp2f(s_m[s][g] - Ms);
+            accd += s_o[s][g][d] * w;
+            lsum += s_l[s][g] * w;
+        }
+        part[g * (D + 2) + 2 + d] = accd;
+        if (d == 0) {
+            part[g * (D + 2)] = M;
+            part[g * (D + 2) + 1] = lsum;
+        }
+    }
+}
+
+template <int D>
+static bool dispatch_fused(int G, dim3 grid, hipStream_t st, const CacheView& src, const uint8_t* keep,
+                           const CacheViewMut& dst, const uint16_t* q, const Shape& sh, const Workspace& ws,
+                           float scale_log2, int lb, int le) {
+    switch (G) {
+#define KVTRIM_CASE(g) \
+    case g: hipLaunchKernelGGL((k_cmp_attn<D, g>), grid, dim3(FUS_THREADS), 0, st, src, keep, dst, q, sh, ws, scale_log2, lb, le); return true;
+        KVTRIM_CASE(1) KVTRIM_CASE(2) KVTRIM_CASE(3) KVTRIM_CASE(4) KVTRIM_CASE(5) KVTRIM_CASE(6) KVTRIM_CASE(7) KVTRIM_CASE(8)
+#undef KVTRIM_CASE
+        default: return false;
+    }
+}
+
+kvtrim_status launch_compact_attn(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const int32_t* kept,
+                                  const CacheViewMut& dst, int32_t reserve, const uint16_t* q, int32_t layer_begin,
+                                  int32_t layer_end, float scale, float* out, float* lse, hipStream_t st) {
+    const Shape& sh = ctx->shape;
+    const Workspace& ws = ctx->ws;
+    const int64_t max_chunks = src.cap / CMP_CHUNK + sh.nseg;
+    if (max_chunks > ws.max_att_chunks) {
+        // Too many source chunks for the partial-result buffer (a first eviction from a long
+        // prefill): run the two stages one after the other, which computes the same thing.
+        kvtrim_status rc = launch_compact(ctx, src, keep, kept, dst, reserve, st);
+        if (rc != KVTRIM_OK) return rc;
+        CacheView d;
+        d.k = dst.k; d.v = dst.v; d.log_beta = dst.log_beta; d.pos = dst.pos;
+        d.seg_start = dst.seg_start; d.seg_len = dst.seg_len; d.cap = dst.cap;
+        return launch_attn(ctx, d, q, layer_begin, layer_end, scale, out, lse, st);
+    }
+    launch_cmp_scan(ctx, src, keep, kept, dst, reserve, st);
+    bool ok;
+    {
+        ProfScope prof(ctx, K_CMP_ATTN, st);
+        const float scale_log2 = scale * 1.4426950408889634f;
+        ok = sh.head_dim == 128
+                 ? dispatch_fused<128>(sh.group, dim3((unsigned)max_chunks), st, src, keep, dst, q, sh, ws, scale_log2, layer_begin, layer_end)
+                 : dispatch_fused<64>(sh.group, dim3((unsigned)max_chunks), st, src, keep, dst, q, sh, ws, scale_log2, layer_begin, layer_end);
+    }
+    if (!ok) return KVTRIM_EINVAL;
+    return launch_combine(ctx, ws.cmp_chunk_prefix, layer_begin, layer_end, out, lse, st);
+}
+
+}  // namespace kvtrim

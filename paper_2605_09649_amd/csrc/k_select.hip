@@ -6,51 +6,48 @@
 // walks the merged histogram from the top to fix the next digits of the threshold key.
 // Entries above the threshold are kept; entries equal to it are kept in storage order
 // (segment ascending, position ascending = layer, head, position) until the budget is
-// met, which needs an ordered count of ties per chunk and an exclusive scan over chunks.
+// met.  When every entry equal to the threshold fits (the usual case) the mask is a plain
+// comparison; otherwise an ordered count of ties per chunk and an exclusive scan over the
+// chunks rank them.
 #include "kvtrim_device.h"
 
 namespace kvtrim {
 
-constexpr int SEL_THREADS = 256;      // mask / count kernels: one chunk per block, 8 entries per thread
+constexpr int SEL_THREADS = 256;      // mask kernel: one chunk per block, 8 entries per thread
 constexpr int CNT_THREADS = 1024;
 constexpr int HIST_THREADS = 1024;    // histogram passes: few fat blocks, so that few device-scope
 constexpr int HIST_BLOCKS = 256;      // atomics meet on one address when the LDS histograms are merged
                                       // (the merged histogram is also kept in HIST_REPLICAS copies)
 constexpr int PLAN_ZERO_BLOCKS = 8;   // extra blocks of the plan kernel that clear the histograms
+constexpr int SEL_SHIFT = 11;         // log2(SEL_CHUNK)
+static_assert((1 << SEL_SHIFT) == SEL_CHUNK, "SEL_SHIFT out of step with SEL_CHUNK");
 
 __global__ __launch_bounds__(1024) void k_sel_plan(CacheView c, Shape sh, const int64_t* __restrict__ budget,
                                                    Workspace ws, int32_t* __restrict__ kept_out) {
-    __shared__ int64_t lds64[17];
     if (blockIdx.x > 0) {                      // clear the (replicated) histograms of the three passes
         const int n = 3 * HIST_REPLICAS * sh.n_seq * RADIX_BINS;
         for (int i = (blockIdx.x - 1) * blockDim.x + threadIdx.x; i < n; i += (gridDim.x - 1) * blockDim.x)
             ws.hist[i] = 0;
         return;
     }
-    build_chunk_table(c.seg_len, c.seg_start, sh.nseg, [](int) { return true; }, SEL_CHUNK, c.cap, ws.sel_chunk_prefix,
-                      ws.sel_chunk_seg, ws.max_sel_chunks, ws.err, lds64);
     for (int i = threadIdx.x; i < 8; i += blockDim.x) ws.done[i] = 0;
     for (int g = threadIdx.x; g < sh.nseg; g += blockDim.x) kept_out[g] = 0;
-    const bool empty = ws.sel_chunk_prefix[sh.nseg] == 0;   // also the state after a layout error
-    for (int seq = 0; seq < sh.n_seq; ++seq) {
-        int64_t n = 0;
-        if (!empty)
-            for (int g = threadIdx.x; g < sh.segs_per_seq; g += blockDim.x) n += c.seg_len[seq * sh.segs_per_seq + g];
-        n = block_sum<int64_t>(n, lds64);
-        if (threadIdx.x == 0) {
-            int64_t b = budget[seq];
-            if (b < 0) b = 0;
-            SelState st;
-            st.prefix = 0;
-            st.thr_key = 0xFFFFFFFFu;
-            st.count = n;
-            st.want = b < n ? b : n;
-            st.rank = st.want;
-            st.tie_quota = 0;
-            st.keep_none = st.want == 0;
-            st.need_rank = 0;
-            ws.sel[seq] = st;
-        }
+    build_chunk_table(c.seg_len, c.seg_start, sh.nseg, [](int) { return true; }, SEL_CHUNK, c.cap,
+                      ws.sel_chunk_prefix, ws.sel_desc, ws.max_sel_chunks, ws.sel_entry_prefix, ws.err);
+    for (int seq = threadIdx.x; seq < sh.n_seq; seq += blockDim.x) {
+        const int64_t n = ws.sel_entry_prefix[(seq + 1) * sh.segs_per_seq] - ws.sel_entry_prefix[seq * sh.segs_per_seq];
+        int64_t b = budget[seq];
+        if (b < 0) b = 0;
+        SelState st;
+        st.prefix = 0;
+        st.thr_key = 0xFFFFFFFFu;
+        st.count = n;
+        st.want = b < n ? b : n;
+        st.rank = st.want;
+        st.tie_quota = 0;
+        st.keep_none = st.want == 0;
+        st.need_rank = 0;
+        ws.sel[seq] = st;
     }
 }
 
@@ -69,13 +66,13 @@ __device__ __forceinline__ bool digit_of(uint32_t key, uint32_t prefix, int* bin
 }
 
 // Histogram of the next digit over the entries whose higher digits equal the prefix found so
-// far.  Blocks take contiguous ranges of chunks; the LDS histogram is flushed when the
-// sequence changes and at the end.  Only one thread per block issues the device-scope fence
-// (a fence per wavefront costs an L2 write-back each and dominated the pass).
+// far.  A block takes a contiguous range of chunks and walks it as a flat range of entry slots
+// (every load independent of the previous one); its LDS histogram is flushed per sequence.
+// Only one thread per block issues the device-scope fence (a fence per wavefront costs an L2
+// write-back each and dominated the pass).
 template <int PASS>
-__global__ __launch_bounds__(HIST_THREADS) void k_sel_hist(CacheView c, const float* __restrict__ score,
-                                                           Shape sh, Workspace ws,
-                                                           uint32_t* __restrict__ thr_out) {
+__global__ __launch_bounds__(HIST_THREADS) void k_sel_hist(const float* __restrict__ score, Shape sh,
+                                                           Workspace ws, uint32_t* __restrict__ thr_out) {
     constexpr int NB = PASS == 2 ? 1024 : 2048;
     __shared__ uint32_t h[NB];
     __shared__ int64_t lds64[17];
@@ -87,42 +84,34 @@ __global__ __launch_bounds__(HIST_THREADS) void k_sel_hist(CacheView c, const fl
     uint32_t* hist_pass = ws.hist + (size_t)PASS * HIST_REPLICAS * sh.n_seq * RADIX_BINS;
     uint32_t* hist = hist_pass + (size_t)(blockIdx.x % HIST_REPLICAS) * sh.n_seq * RADIX_BINS;
 
-    for (int i = tid; i < NB; i += HIST_THREADS) h[i] = 0;
-    __syncthreads();
-    int cur_seq = -1;
-    uint32_t prefix = 0;
-    bool skip = false;
-    for (int ch = c0; ch < c1; ++ch) {
-        const int seg = ws.sel_chunk_seg[ch];
-        const int seq = seg / sh.segs_per_seq;
-        if (seq != cur_seq) {
-            if (cur_seq >= 0) {
-                __syncthreads();
-                for (int i = tid; i < NB; i += HIST_THREADS) {
-                    uint32_t v = h[i];
-                    if (v) atomicAdd(&hist[(size_t)cur_seq * RADIX_BINS + i], v);
+    if (c0 < c1) {
+        for (int i = tid; i < NB; i += HIST_THREADS) h[i] = 0;
+        const int seq_lo = ws.sel_desc[c0].seg / sh.segs_per_seq;
+        const int seq_hi = ws.sel_desc[c1 - 1].seg / sh.segs_per_seq;
+        for (int seq = seq_lo; seq <= seq_hi; ++seq) {
+            const int a = max(c0, ws.sel_chunk_prefix[seq * sh.segs_per_seq]);
+            const int b = min(c1, ws.sel_chunk_prefix[(seq + 1) * sh.segs_per_seq]);
+            if (a >= b) continue;
+            const uint32_t prefix = ws.sel[seq].prefix;
+            if (ws.sel[seq].keep_none) continue;
+            __syncthreads();
+#pragma unroll 4
+            for (int64_t slot = ((int64_t)a << SEL_SHIFT) + tid; slot < ((int64_t)b << SEL_SHIFT); slot += HIST_THREADS) {
+                const ChunkDesc d = ws.sel_desc[slot >> SEL_SHIFT];
+                const int j = (int)(slot & (SEL_CHUNK - 1));
+                if (j < d.n) {
+                    int bin;
+                    if (digit_of<PASS>(key_of_score(score[d.first + j]), prefix, &bin)) atomicAdd(&h[bin], 1u);
+                }
+            }
+            __syncthreads();
+            for (int i = tid; i < NB; i += HIST_THREADS) {
+                const uint32_t v = h[i];
+                if (v) {
+                    atomicAdd(&hist[(size_t)seq * RADIX_BINS + i], v);
                     h[i] = 0;
                 }
-                __syncthreads();
             }
-            cur_seq = seq;
-            prefix = ws.sel[seq].prefix;
-            skip = ws.sel[seq].keep_none != 0;
-        }
-        if (skip) continue;
-        const int off = (ch - ws.sel_chunk_prefix[seg]) * SEL_CHUNK;
-        const int end = min(c.seg_len[seg], off + SEL_CHUNK);
-        const float* s = score + c.seg_start[seg];
-        for (int j = off + tid; j < end; j += HIST_THREADS) {
-            int bin;
-            if (digit_of<PASS>(key_of_score(s[j]), prefix, &bin)) atomicAdd(&h[bin], 1u);
-        }
-    }
-    __syncthreads();
-    if (cur_seq >= 0) {
-        for (int i = tid; i < NB; i += HIST_THREADS) {
-            uint32_t v = h[i];
-            if (v) atomicAdd(&hist[(size_t)cur_seq * RADIX_BINS + i], v);
         }
     }
     __syncthreads();
@@ -187,9 +176,8 @@ __global__ __launch_bounds__(HIST_THREADS) void k_sel_hist(CacheView c, const fl
 // chunk of such a sequence: entries above the threshold (credited to the segment) and entries
 // equal to it; the last block then turns the per-chunk tie counts into exclusive prefixes per
 // sequence and credits the ties that fit into the quota to their segments.
-__global__ __launch_bounds__(CNT_THREADS) void k_sel_count(CacheView c, const float* __restrict__ score,
-                                                           Shape sh, Workspace ws,
-                                                           int32_t* __restrict__ kept_out) {
+__global__ __launch_bounds__(CNT_THREADS) void k_sel_count(const float* __restrict__ score, Shape sh,
+                                                           Workspace ws, int32_t* __restrict__ kept_out) {
     __shared__ int64_t lds64[17];
     __shared__ int32_t lds32[17];
     __shared__ int is_last;
@@ -198,22 +186,19 @@ __global__ __launch_bounds__(CNT_THREADS) void k_sel_count(CacheView c, const fl
     const int total = ws.sel_chunk_prefix[sh.nseg];
     const int ch = blockIdx.x;
     if (ch < total) {
-        const int seg = ws.sel_chunk_seg[ch];
-        const SelState st = ws.sel[seg / sh.segs_per_seq];
+        const ChunkDesc d = ws.sel_desc[ch];
+        const SelState st = ws.sel[d.seg / sh.segs_per_seq];
         if (st.need_rank) {
             int gt = 0, eq = 0;
-            const int off = (ch - ws.sel_chunk_prefix[seg]) * SEL_CHUNK;
-            const int end = min(c.seg_len[seg], off + SEL_CHUNK);
-            const float* s = score + c.seg_start[seg];
-            for (int j = off + tid; j < end; j += CNT_THREADS) {
-                const uint32_t key = key_of_score(s[j]);
+            for (int j = tid; j < d.n; j += CNT_THREADS) {
+                const uint32_t key = key_of_score(score[d.first + j]);
                 gt += key > st.thr_key;
                 eq += key == st.thr_key;
             }
             gt = block_sum<int32_t>(gt, lds32);
             eq = block_sum<int32_t>(eq, lds32);
             if (tid == 0) {
-                if (gt) atomicAdd(&kept_out[seg], gt);
+                if (gt) atomicAdd(&kept_out[d.seg], gt);
                 ws.chunk_eq[ch] = eq;
             }
         }
@@ -243,7 +228,7 @@ __global__ __launch_bounds__(CNT_THREADS) void k_sel_count(CacheView c, const fl
                 ws.chunk_tie_base[cc] = tb;
                 if (v > 0 && tb < quota) {
                     const int64_t take = min(v, quota - tb);
-                    atomicAdd(&kept_out[ws.sel_chunk_seg[cc]], (int32_t)take);
+                    atomicAdd(&kept_out[ws.sel_desc[cc].seg], (int32_t)take);
                 }
             }
             running += tot;
@@ -254,58 +239,57 @@ __global__ __launch_bounds__(CNT_THREADS) void k_sel_count(CacheView c, const fl
 // keep[e] = key > thr, or key == thr and the entry is among the first `quota` ties of its
 // sequence in storage order.  When every tie fits (the usual case) the kernel also counts the
 // survivors of its chunk into kept_out; otherwise k_sel_count has done that.
-__global__ __launch_bounds__(SEL_THREADS) void k_sel_mask(CacheView c, const float* __restrict__ score,
-                                                          Shape sh, Workspace ws, uint8_t* __restrict__ keep,
+__global__ __launch_bounds__(SEL_THREADS) void k_sel_mask(const float* __restrict__ score, Shape sh,
+                                                          Workspace ws, uint8_t* __restrict__ keep,
                                                           int32_t* __restrict__ kept_out) {
     __shared__ int32_t lds32[17];
     const int tid = threadIdx.x;
     const int total = ws.sel_chunk_prefix[sh.nseg];
     const int ch = blockIdx.x;
     if (ch >= total) return;
-    const int seg = ws.sel_chunk_seg[ch];
-    const SelState st = ws.sel[seg / sh.segs_per_seq];
-    const int off = (ch - ws.sel_chunk_prefix[seg]) * SEL_CHUNK;
-    const int end = min(c.seg_len[seg], off + SEL_CHUNK);
-    const float* s = score + c.seg_start[seg];
-    uint8_t* kp = keep + c.seg_start[seg];
+    const ChunkDesc d = ws.sel_desc[ch];
+    const SelState st = ws.sel[d.seg / sh.segs_per_seq];
+    const float* s = score + d.first;
+    uint8_t* kp = keep + d.first;
     if (st.keep_none) {
-        for (int j = off + tid; j < end; j += SEL_THREADS) kp[j] = 0;
+        for (int j = tid; j < d.n; j += SEL_THREADS) kp[j] = 0;
         return;
     }
     if (!st.need_rank) {                                          // every tie survives
         int n = 0;
-        for (int j = off + tid; j < end; j += SEL_THREADS) {
+#pragma unroll 8
+        for (int j = tid; j < d.n; j += SEL_THREADS) {
             const bool k = key_of_score(s[j]) >= st.thr_key;
             kp[j] = k;
             n += k;
         }
         n = block_sum<int32_t>(n, lds32);
-        if (tid == 0 && n) atomicAdd(&kept_out[seg], n);
+        if (tid == 0 && n) atomicAdd(&kept_out[d.seg], n);
         return;
     }
     const int64_t tb = ws.chunk_tie_base[ch];
     const int eq_total = ws.chunk_eq[ch];
     if (eq_total == 0 || tb + eq_total <= st.tie_quota) {        // every tie of this chunk survives
-        for (int j = off + tid; j < end; j += SEL_THREADS) kp[j] = key_of_score(s[j]) >= st.thr_key;
+        for (int j = tid; j < d.n; j += SEL_THREADS) kp[j] = key_of_score(s[j]) >= st.thr_key;
         return;
     }
     if (tb >= st.tie_quota) {                                     // no tie of this chunk survives
-        for (int j = off + tid; j < end; j += SEL_THREADS) kp[j] = key_of_score(s[j]) > st.thr_key;
+        for (int j = tid; j < d.n; j += SEL_THREADS) kp[j] = key_of_score(s[j]) > st.thr_key;
         return;
     }
     // the quota runs out inside this chunk: rank the ties in order
     int64_t running = tb;
-    for (int base = off; base < end; base += SEL_THREADS) {       // uniform trip count
+    for (int base = 0; base < d.n; base += SEL_THREADS) {         // uniform trip count
         const int j = base + tid;
         uint32_t key = 0;
         int is_eq = 0;
-        if (j < end) {
+        if (j < d.n) {
             key = key_of_score(s[j]);
             is_eq = key == st.thr_key;
         }
         int32_t tot;
         int32_t ex = block_excl_scan<int32_t>(is_eq, lds32, &tot);
-        if (j < end) kp[j] = key > st.thr_key || (is_eq && running + ex < st.tie_quota);
+        if (j < d.n) kp[j] = key > st.thr_key || (is_eq && running + ex < st.tie_quota);
         running += tot;
     }
 }
@@ -320,15 +304,15 @@ kvtrim_status launch_select(kvtrim_ctx* ctx, const CacheView& c, const float* sc
     { ProfScope prof(ctx, K_SEL_PLAN, st);
       hipLaunchKernelGGL(k_sel_plan, dim3(1 + PLAN_ZERO_BLOCKS), dim3(1024), 0, st, c, sh, budget, ws, kept); }
     { ProfScope prof(ctx, K_SEL_HIST0, st);
-      hipLaunchKernelGGL(k_sel_hist<0>, dim3(hist_blocks), dim3(HIST_THREADS), 0, st, c, score, sh, ws, thr); }
+      hipLaunchKernelGGL(k_sel_hist<0>, dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, thr); }
     { ProfScope prof(ctx, K_SEL_HIST1, st);
-      hipLaunchKernelGGL(k_sel_hist<1>, dim3(hist_blocks), dim3(HIST_THREADS), 0, st, c, score, sh, ws, thr); }
+      hipLaunchKernelGGL(k_sel_hist<1>, dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, thr); }
     { ProfScope prof(ctx, K_SEL_HIST2, st);
-      hipLaunchKernelGGL(k_sel_hist<2>, dim3(hist_blocks), dim3(HIST_THREADS), 0, st, c, score, sh, ws, thr); }
+      hipLaunchKernelGGL(k_sel_hist<2>, dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, thr); }
     { ProfScope prof(ctx, K_SEL_COUNT, st);
-      hipLaunchKernelGGL(k_sel_count, dim3(n_chunk_blocks), dim3(CNT_THREADS), 0, st, c, score, sh, ws, kept); }
+      hipLaunchKernelGGL(k_sel_count, dim3(n_chunk_blocks), dim3(CNT_THREADS), 0, st, score, sh, ws, kept); }
     { ProfScope prof(ctx, K_SEL_MASK, st);
-      hipLaunchKernelGGL(k_sel_mask, dim3(n_chunk_blocks), dim3(SEL_THREADS), 0, st, c, score, sh, ws, keep, kept); }
+      hipLaunchKernelGGL(k_sel_mask, dim3(n_chunk_blocks), dim3(SEL_THREADS), 0, st, score, sh, ws, keep, kept); }
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;
 }

@@ -57,19 +57,20 @@ static Layout layout_of(const kvtrim_config* c) {
     l.max_att_chunks = att;
     size_t cur = 0;
     l.off[0] = bump(cur, (nseg + 1) * sizeof(int32_t));                        // sel_chunk_prefix
-    l.off[1] = bump(cur, l.max_sel_chunks * sizeof(int32_t));                  // sel_chunk_seg
+    l.off[1] = bump(cur, l.max_sel_chunks * sizeof(ChunkDesc));                // sel_desc
     l.off[2] = bump(cur, (size_t)3 * HIST_REPLICAS * c->n_seq * RADIX_BINS * sizeof(uint32_t)); // hist
     l.off[3] = bump(cur, (size_t)c->n_seq * sizeof(SelState));                 // sel
     l.off[4] = bump(cur, 8 * sizeof(uint32_t));                                // done
     l.off[5] = bump(cur, l.max_sel_chunks * sizeof(int32_t));                  // chunk_eq
     l.off[6] = bump(cur, l.max_sel_chunks * sizeof(int64_t));                  // chunk_tie_base
     l.off[7] = bump(cur, (nseg + 1) * sizeof(int32_t));                        // cmp_chunk_prefix
-    l.off[8] = bump(cur, l.max_cmp_chunks * sizeof(int32_t));                  // cmp_chunk_seg
+    l.off[8] = bump(cur, l.max_cmp_chunks * sizeof(ChunkDesc));                // cmp_desc
     l.off[9] = bump(cur, l.max_cmp_chunks * sizeof(int64_t));                  // cmp_chunk_dst
     l.off[10] = bump(cur, (nseg + 1) * sizeof(int32_t));                       // att_chunk_prefix
-    l.off[11] = bump(cur, l.max_att_chunks * sizeof(int32_t));                 // att_chunk_seg
+    l.off[11] = bump(cur, l.max_att_chunks * sizeof(ChunkDesc));               // att_desc
     l.off[12] = bump(cur, (size_t)l.max_att_chunks * G * (c->head_dim + 2) * sizeof(float)); // att_partial
     l.off[13] = bump(cur, 256);                                                // err
+    l.off[14] = bump(cur, (nseg + 1) * sizeof(int64_t));                       // sel_entry_prefix
     l.total = (cur + 255) & ~(size_t)255;
     return l;
 }
@@ -162,19 +163,20 @@ kvtrim_status kvtrim_create(kvtrim_ctx** out, const kvtrim_config* cfg) {
     char* b = (char*)ctx->ws_base;
     Workspace& w = ctx->ws;
     w.sel_chunk_prefix = (int32_t*)(b + l.off[0]);
-    w.sel_chunk_seg = (int32_t*)(b + l.off[1]);
+    w.sel_desc = (ChunkDesc*)(b + l.off[1]);
     w.hist = (uint32_t*)(b + l.off[2]);
     w.sel = (SelState*)(b + l.off[3]);
     w.done = (uint32_t*)(b + l.off[4]);
     w.chunk_eq = (int32_t*)(b + l.off[5]);
     w.chunk_tie_base = (int64_t*)(b + l.off[6]);
     w.cmp_chunk_prefix = (int32_t*)(b + l.off[7]);
-    w.cmp_chunk_seg = (int32_t*)(b + l.off[8]);
+    w.cmp_desc = (ChunkDesc*)(b + l.off[8]);
     w.cmp_chunk_dst = (int64_t*)(b + l.off[9]);
     w.att_chunk_prefix = (int32_t*)(b + l.off[10]);
-    w.att_chunk_seg = (int32_t*)(b + l.off[11]);
+    w.att_desc = (ChunkDesc*)(b + l.off[11]);
     w.att_partial = (float*)(b + l.off[12]);
     w.err = (int32_t*)(b + l.off[13]);
+    w.sel_entry_prefix = (int64_t*)(b + l.off[14]);
     w.max_sel_chunks = l.max_sel_chunks;
     w.max_cmp_chunks = l.max_cmp_chunks;
     w.max_att_chunks = l.max_att_chunks;
@@ -197,7 +199,7 @@ static void free_profile(kvtrim_ctx* ctx) {
 
 static const char* const kernel_names[KVTRIM_N_KERNELS] = {
     "k_score", "k_sel_plan", "k_sel_hist<0>", "k_sel_hist<1>", "k_sel_hist<2>", "k_sel_count", "k_sel_mask",
-    "k_cmp_scan", "k_cmp_copy", "k_att_plan", "k_att_partial", "k_att_combine", "k_append"};
+    "k_cmp_scan", "k_cmp_copy", "k_att_plan", "k_att_partial", "k_att_combine", "k_append", "k_cmp_attn"};
 
 const char* kvtrim_kernel_name(int32_t id) { return id >= 0 && id < KVTRIM_N_KERNELS ? kernel_names[id] : nullptr; }
 
@@ -312,6 +314,26 @@ kvtrim_status kvtrim_decode_attn(kvtrim_ctx* ctx, const kvtrim_cache* c, const v
     if (!(softmax_scale == softmax_scale)) return invalid(ctx, "softmax_scale is NaN");
     return launch_attn(ctx, view_of(c), (const uint16_t*)q, layer_begin, layer_end, softmax_scale, out, lse,
                        (hipStream_t)hip_stream);
+}
+
+kvtrim_status kvtrim_compact_attn(kvtrim_ctx* ctx, const kvtrim_cache* src, const uint8_t* keep, const int32_t* kept,
+                                  kvtrim_cache* dst, int32_t reserve, const void* q, int32_t layer_begin,
+                                  int32_t layer_end, float softmax_scale, float* out, float* lse, void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    if (const char* p = cache_problem(ctx, src, true)) return invalid(ctx, p);
+    if (const char* p = cache_problem(ctx, dst, true)) return invalid(ctx, p);
+    if (!keep || !kept) return invalid(ctx, "keep / kept is NULL");
+    if (reserve < 0) return invalid(ctx, "reserve < 0");
+    if (src->k == dst->k || src->v == dst->v || src->log_beta == dst->log_beta || src->pos == dst->pos ||
+        src->seg_start == dst->seg_start || src->seg_len == dst->seg_len)
+        return invalid(ctx, "src and dst share a buffer");
+    if (!q || !out) return invalid(ctx, "q / out is NULL");
+    if (((uintptr_t)q) & 15) return invalid(ctx, "q not 16-byte aligned");
+    if (layer_begin < 0 || layer_end > ctx->cfg.n_layers || layer_begin >= layer_end)
+        return invalid(ctx, "empty or out-of-range layer range");
+    if (!(softmax_scale == softmax_scale)) return invalid(ctx, "softmax_scale is NaN");
+    return launch_compact_attn(ctx, view_of(src), keep, kept, view_mut_of(dst), reserve, (const uint16_t*)q,
+                               layer_begin, layer_end, softmax_scale, out, lse, (hipStream_t)hip_stream);
 }
 
 kvtrim_status kvtrim_append(kvtrim_ctx* ctx, kvtrim_cache* c, const void* k_new, const void* v_new,

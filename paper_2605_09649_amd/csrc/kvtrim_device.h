@@ -55,55 +55,112 @@ __device__ __forceinline__ T block_sum(T v, T* lds) {
     return s;
 }
 
-// Chunk table of a ragged cache, built by ONE block: segment g with in_range(g) has
-// ceil(seg_len[g] / chunk) chunks (0 for the other segments);
-// prefix[g] = first chunk of segment g, prefix[nseg] = number of chunks, chunk_seg[c] = segment
-// of chunk c.  Also checks every segment against `cap` and the chunk count against `max_chunks`
-// (ERR_LAYOUT; the table is then left empty).  `lds64` needs 17 int64.
+// Chunk table of a ragged cache, built by ONE block (blockDim.x <= 1024): segment g with
+// in_range(g) is cut into ceil(seg_len[g] / chunk) chunks (none for the other segments);
+// prefix[g] = first chunk of segment g, prefix[nseg] = number of chunks, desc[c] = entries and
+// segment of chunk c.  Returns the number of chunks.  Every segment is checked against `cap`
+// and its successor, the chunk count against `max_chunks` (ERR_LAYOUT; the table is then left
+// empty).  Optionally writes entry_prefix[g] = entries of the in-range segments before g
+// (entry_prefix[nseg] = all of them).
+// Segments with few chunks are filled by the thread that scanned them; long ones are queued
+// in LDS and filled by whole wavefronts.
 template <typename InRange>
-__device__ __forceinline__ void build_chunk_table(const int32_t* __restrict__ seg_len,
-                                                  const int64_t* __restrict__ seg_start, int nseg,
-                                                  InRange in_range, int chunk, int64_t cap,
-                                                  int32_t* prefix, int32_t* chunk_seg, int64_t max_chunks,
-                                                  int32_t* err, int64_t* lds64) {
-    __shared__ int bad;
-    if (threadIdx.x == 0) bad = 0;
+__device__ __forceinline__ int build_chunk_table(const int32_t* __restrict__ seg_len,
+                                                 const int64_t* __restrict__ seg_start, int nseg,
+                                                 InRange in_range, int chunk, int64_t cap,
+                                                 int32_t* prefix, ChunkDesc* desc, int64_t max_chunks,
+                                                 int64_t* entry_prefix, int32_t* err) {
+    constexpr int SMALL = 16;
+    __shared__ uint64_t s_scan[17];
+    __shared__ int s_bad, s_nbig;
+    __shared__ int s_big_g[1024], s_big_c0[1024];
+    if (threadIdx.x == 0) s_bad = 0;
     __syncthreads();
-    int64_t carry = 0;
+    // pass 1: validate and count (chunks in the low, entries in the high 32 bits of one scan)
+    uint64_t carry = 0;
     for (int base = 0; base < nseg; base += blockDim.x) {
-        int g = base + threadIdx.x;
-        int64_t n = 0;
+        const int g = base + threadIdx.x;
+        uint64_t v = 0;
         if (g < nseg) {
-            int len = seg_len[g];
-            int64_t st = seg_start[g];
-            int64_t nxt = (g + 1 < nseg) ? seg_start[g + 1] : cap;
-            if (len < 0 || st < 0 || st + len > cap || st + len > nxt) bad = 1;
-            if (in_range(g) && len > 0) n = (len + chunk - 1) / chunk;
+            const int len = seg_len[g];
+            const int64_t st = seg_start[g];
+            const int64_t nxt = (g + 1 < nseg) ? seg_start[g + 1] : cap;
+            if (len < 0 || st < 0 || st + len > cap || st + len > nxt) s_bad = 1;
+            else if (in_range(g) && len > 0) v = ((uint64_t)len << 32) | (uint64_t)((len + chunk - 1) / chunk);
         }
-        int64_t tot;
-        int64_t ex = block_excl_scan<int64_t>(n, lds64, &tot);
-        if (g < nseg) prefix[g] = (int32_t)min(carry + ex, (int64_t)0x7fffffff);
+        uint64_t tot;
+        block_excl_scan<uint64_t>(v, s_scan, &tot);
         carry += tot;
     }
     __syncthreads();
-    if (bad || carry > max_chunks) {
+    const int64_t total = (int64_t)(carry & 0xffffffffu);
+    if (s_bad || total > max_chunks || (carry >> 32) > (uint64_t)cap) {
         if (threadIdx.x == 0) atomicOr(err, ERR_LAYOUT);
-        for (int g = threadIdx.x; g <= nseg; g += blockDim.x) prefix[g] = 0;
+        for (int g = threadIdx.x; g <= nseg; g += blockDim.x) {
+            prefix[g] = 0;
+            if (entry_prefix) entry_prefix[g] = 0;
+        }
         __syncthreads();
-        return;
+        return 0;
     }
-    if (threadIdx.x == 0) prefix[nseg] = (int32_t)carry;
-    __syncthreads();
-    // one wavefront per segment, lanes stride over its chunks
-    const int lane = lane_id(), wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-    for (int g = wave; g < nseg; g += nw) {
-        if (!in_range(g)) continue;
-        int c0 = prefix[g];
-        int len = seg_len[g];
-        int n = len > 0 ? (len + chunk - 1) / chunk : 0;
-        for (int i = lane; i < n; i += 64) chunk_seg[c0 + i] = g;
+    // pass 2: prefixes and descriptors
+    carry = 0;
+    for (int base = 0; base < nseg; base += blockDim.x) {
+        const int g = base + threadIdx.x;
+        uint64_t v = 0;
+        int len = 0;
+        int64_t st = 0;
+        if (g < nseg) {
+            len = seg_len[g];
+            st = seg_start[g];
+            if (in_range(g) && len > 0) v = ((uint64_t)len << 32) | (uint64_t)((len + chunk - 1) / chunk);
+        }
+        if (threadIdx.x == 0) s_nbig = 0;
+        uint64_t tot;
+        const uint64_t ex = carry + block_excl_scan<uint64_t>(v, s_scan, &tot);
+        carry += tot;
+        const int c0 = (int)(ex & 0xffffffffu);
+        const int n = (int)(v & 0xffffffffu);
+        if (g < nseg) {
+            prefix[g] = c0;
+            if (entry_prefix) entry_prefix[g] = (int64_t)(ex >> 32);
+            if (n > SMALL) {
+                const int slot = atomicAdd(&s_nbig, 1);
+                s_big_g[slot] = g;
+                s_big_c0[slot] = c0;
+            } else {
+                for (int i = 0; i < n; ++i) {
+                    ChunkDesc d;
+                    d.first = st + (int64_t)i * chunk;
+                    d.n = min(chunk, len - i * chunk);
+                    d.seg = g;
+                    desc[c0 + i] = d;
+                }
+            }
+        }
+        __syncthreads();
+        const int lane = lane_id(), wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+        for (int b = wave; b < s_nbig; b += nw) {
+            const int gg = s_big_g[b], cc = s_big_c0[b];
+            const int ll = seg_len[gg];
+            const int64_t ss = seg_start[gg];
+            const int nn = (ll + chunk - 1) / chunk;
+            for (int i = lane; i < nn; i += 64) {
+                ChunkDesc d;
+                d.first = ss + (int64_t)i * chunk;
+                d.n = min(chunk, ll - i * chunk);
+                d.seg = gg;
+                desc[cc + i] = d;
+            }
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        prefix[nseg] = (int32_t)(carry & 0xffffffffu);
+        if (entry_prefix) entry_prefix[nseg] = (int64_t)(carry >> 32);
     }
     __syncthreads();
+    return (int)total;
 }
 
 }  // namespace kvtrim

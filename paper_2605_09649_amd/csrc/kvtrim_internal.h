@@ -55,10 +55,18 @@ struct SelState {
     int32_t need_rank;   // only some of the entries equal to thr_key fit: they must be ranked in order
 };
 
+// One chunk of a segment: entries [first, first + n) of the flat arrays.
+struct ChunkDesc {
+    int64_t first;
+    int32_t n;
+    int32_t seg;
+};
+
 struct Workspace {
     // selection
     int32_t* sel_chunk_prefix;   // [nseg+1] first chunk of each segment
-    int32_t* sel_chunk_seg;      // [max_sel_chunks] segment of each chunk
+    ChunkDesc* sel_desc;         // [max_sel_chunks]
+    int64_t* sel_entry_prefix;   // [nseg+1] entries before each segment
     uint32_t* hist;              // [3][HIST_REPLICAS][n_seq][RADIX_BINS]
     SelState* sel;               // [n_seq]
     uint32_t* done;              // [8] "last block" counters
@@ -66,11 +74,11 @@ struct Workspace {
     int64_t* chunk_tie_base;     // [max_sel_chunks] ties of the sequence before the chunk
     // compaction
     int32_t* cmp_chunk_prefix;   // [nseg+1]
-    int32_t* cmp_chunk_seg;      // [max_cmp_chunks]
+    ChunkDesc* cmp_desc;         // [max_cmp_chunks]
     int64_t* cmp_chunk_dst;      // [max_cmp_chunks] first dst entry of the chunk's survivors
     // attention
     int32_t* att_chunk_prefix;   // [nseg+1]
-    int32_t* att_chunk_seg;      // [max_att_chunks]
+    ChunkDesc* att_desc;         // [max_att_chunks]
     float* att_partial;          // [max_att_chunks][G][D+2]  (m, l, o[D]) per query head
     int32_t* err;                // sticky device flag
     int64_t max_sel_chunks, max_cmp_chunks, max_att_chunks;
@@ -81,7 +89,7 @@ struct Workspace {
 namespace kvtrim {
 enum KernelId {
     K_SCORE = 0, K_SEL_PLAN, K_SEL_HIST0, K_SEL_HIST1, K_SEL_HIST2, K_SEL_COUNT, K_SEL_MASK,
-    K_CMP_SCAN, K_CMP_COPY, K_ATT_PLAN, K_ATT_PARTIAL, K_ATT_COMBINE, K_APPEND, K_COUNT
+    K_CMP_SCAN, K_CMP_COPY, K_ATT_PLAN, K_ATT_PARTIAL, K_ATT_COMBINE, K_APPEND, K_CMP_ATTN, K_COUNT
 };
 static_assert(K_COUNT == KVTRIM_N_KERNELS, "kernel table out of step with the header");
 }  // namespace kvtrim
@@ -116,6 +124,14 @@ kvtrim_status launch_compact(kvtrim_ctx*, const CacheView& src, const uint8_t* k
                              const CacheViewMut& dst, int32_t reserve, hipStream_t);
 kvtrim_status launch_attn(kvtrim_ctx*, const CacheView&, const uint16_t* q, int32_t layer_begin,
                           int32_t layer_end, float scale, float* out, float* lse, hipStream_t);
+void launch_cmp_scan(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const int32_t* kept,
+                     const CacheViewMut& dst, int32_t reserve, hipStream_t);
+kvtrim_status launch_combine(kvtrim_ctx*, const int32_t* chunk_prefix, int32_t layer_begin, int32_t layer_end,
+                             float* out, float* lse, hipStream_t);
+kvtrim_status launch_compact_attn(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const int32_t* kept,
+                                  const CacheViewMut& dst, int32_t reserve, const uint16_t* q,
+                                  int32_t layer_begin, int32_t layer_end, float scale, float* out, float* lse,
+                                  hipStream_t);
 kvtrim_status launch_append(kvtrim_ctx*, const CacheViewMut&, const uint16_t* k_new, const uint16_t* v_new,
                             const float* lb_new, const int32_t* pos_new, int32_t n_new, hipStream_t);
 

@@ -39,8 +39,8 @@ def attn_error(out_gpu, out_ref):
 class GpuLoop:
     """Device-side state of the decode loop: ping-pong caches and the per-step scratch outputs."""
 
-    def __init__(self, w, cache_dict, budget, reserve, extra_entries, device):
-        self.w, self.device, self.reserve = w, device, reserve
+    def __init__(self, w, cache_dict, budget, reserve, extra_entries, device, fused=False):
+        self.w, self.device, self.reserve, self.fused = w, device, reserve, fused
         self.src = kv.Cache.from_dict(cache_dict, device)
         total = int(cache_dict["seg_len"].sum())
         dst_cap = min(int(sum(budget)), total + extra_entries) + w.nseg * reserve + 8
@@ -64,8 +64,12 @@ class GpuLoop:
         kv.kvtrim_score(ctx, self.src, now_dev, self.score)
         kv.kvtrim_select_global(ctx, self.src, self.score, self.budget, self.keep, self.kept, self.thr)
         dst = self.spare[self.flip]
-        kv.kvtrim_compact(ctx, self.src, self.keep, self.kept, dst, self.reserve)
-        kv.kvtrim_decode_attn(ctx, dst, inp["q"], 0, self.w.n_layers, self.scale, self.out, self.lse)
+        if self.fused:
+            kv.kvtrim_compact_attn(ctx, self.src, self.keep, self.kept, dst, self.reserve, inp["q"], 0,
+                                   self.w.n_layers, self.scale, self.out, self.lse)
+        else:
+            kv.kvtrim_compact(ctx, self.src, self.keep, self.kept, dst, self.reserve)
+            kv.kvtrim_decode_attn(ctx, dst, inp["q"], 0, self.w.n_layers, self.scale, self.out, self.lse)
         return dst
 
     def advance(self, dst):
@@ -75,13 +79,13 @@ class GpuLoop:
         self.flip ^= 1
 
 
-def run_steps_both(w, steps, budget, device="cuda:0", reserve=1, cache_dict=None, now0=None):
+def run_steps_both(w, steps, budget, device="cuda:0", reserve=1, cache_dict=None, now0=None, fused=False):
     """Returns one dict per step with the comparison results."""
     if cache_dict is None:
         cache_dict = ki.prefill_cache(w, reserve=reserve)
         now0 = [t - 1 for t in w.prefill]
     hc = host_cache(w, cache_dict)
-    gpu = GpuLoop(w, cache_dict, budget, reserve, steps * w.nseg, device)
+    gpu = GpuLoop(w, cache_dict, budget, reserve, steps * w.nseg, device, fused=fused)
     budget_np = np.array(list(budget), np.int64)
     now = np.array(now0, np.int32)
     per_seq = w.n_layers * w.n_kv_heads

@@ -36,21 +36,24 @@ def wl(S, L, H, G, D, name="t"):
 
 # ---------------------------------------------------------------------------------- whole loop
 
-def test_tiny_workload_full_loop():
+@pytest.mark.parametrize("fused", [False, True])
+def test_tiny_workload_full_loop(fused):
     w = ki.workload("tiny")                       # L4 H4 G2 D64, 2048 prefilled, B = 1024, 16 steps
-    check(run_steps_both(w, steps=16, budget=w.budget, device=DEV))
+    check(run_steps_both(w, steps=16, budget=w.budget, device=DEV, fused=fused))
 
 
+@pytest.mark.parametrize("fused", [False, True])
 @pytest.mark.parametrize("name,prefill,steps", [("llama", 700, 3), ("long", 900, 3), ("vlm", 640, 3),
                                                 ("multiturn", 600, 2)])
-def test_scaled_down_workloads(name, prefill, steps):
+def test_scaled_down_workloads(name, prefill, steps, fused):
     w = ki.workload(name, prefill=prefill)
-    check(run_steps_both(w, steps=steps, budget=w.budget, device=DEV))
+    check(run_steps_both(w, steps=steps, budget=w.budget, device=DEV, fused=fused))
 
 
+@pytest.mark.parametrize("fused", [False, True])
 @pytest.mark.parametrize("S,L,H,G,D", [(1, 2, 2, 1, 128), (2, 2, 1, 7, 128), (1, 1, 3, 8, 64), (3, 1, 2, 3, 64),
-                                       (1, 2, 2, 5, 128), (1, 1, 2, 6, 128)])
-def test_ragged_segments_spanning_several_chunks(S, L, H, G, D):
+                                       (1, 2, 2, 5, 128), (1, 1, 2, 6, 128), (1, 2, 1, 4, 128), (1, 1, 2, 2, 64)])
+def test_ragged_segments_spanning_several_chunks(S, L, H, G, D, fused):
     w = wl(S, L, H, G, D)
     rng = np.random.default_rng(S * 1000 + G * 10 + D)
     seg_len = rng.integers(0, 6000, w.nseg)
@@ -59,14 +62,44 @@ def test_ragged_segments_spanning_several_chunks(S, L, H, G, D):
     c, now = ki.ragged_cache(w, seg_len, reserve=1, salt=G)
     per_seq = [int(seg_len[s * L * H:(s + 1) * L * H].sum()) for s in range(S)]
     budget = [max(1, n // 3) for n in per_seq]
-    check(run_steps_both(w, steps=2, budget=budget, device=DEV, cache_dict=c, now0=now.numpy()))
+    check(run_steps_both(w, steps=2, budget=budget, device=DEV, cache_dict=c, now0=now.numpy(), fused=fused))
 
 
-def test_one_giant_segment_and_many_empty_ones():
+@pytest.mark.parametrize("fused", [False, True])
+def test_one_giant_segment_and_many_empty_ones(fused):
     w = wl(1, 2, 4, 4, 128)
     seg_len = [0, 0, 0, 70001, 0, 0, 3, 0]
     c, now = ki.ragged_cache(w, seg_len, reserve=1, salt=3)
-    check(run_steps_both(w, steps=2, budget=[20011], device=DEV, cache_dict=c, now0=now.numpy()))
+    check(run_steps_both(w, steps=2, budget=[20011], device=DEV, cache_dict=c, now0=now.numpy(), fused=fused))
+
+
+def test_fused_call_with_a_layer_range_and_sparse_mask():
+    # fused compaction + attention on a mask that keeps about one entry in five, layers [1, 3) only
+    w = wl(2, 3, 2, 4, 128)
+    rng = np.random.default_rng(21)
+    seg_len = rng.integers(0, 2500, w.nseg)
+    c, _ = ki.ragged_cache(w, seg_len, salt=21)
+    hc = host_cache(w, c)
+    keep_np = (rng.random(hc.cap) < 0.2).astype(np.uint8)
+    kept_np = np.array([keep_np[s:s + n].sum() for s, n in zip(hc.seg_start, hc.seg_len)], np.int32)
+    dst_cap = int(kept_np.sum()) + 2 * w.nseg
+    dst_ref = oracle.compact(hc, keep_np, dst_cap, 2)
+    q = ki.decode_inputs(w, 3)["q"]
+    scale = 1.0 / math.sqrt(128)
+    ref, ref_lse = oracle.attend(dst_ref, bf16_bits(q), scale)
+    ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, 128, hc.cap)
+    dst = kv.Cache.empty(w.nseg, 128, dst_cap, DEV)
+    out = torch.full(ref.shape, 99.0, dtype=torch.float32, device=DEV)
+    lse = torch.full(ref_lse.shape, 99.0, dtype=torch.float32, device=DEV)
+    kv.kvtrim_compact_attn(ctx, kv.Cache.from_dict(c, DEV), torch.from_numpy(keep_np).to(DEV),
+                           torch.from_numpy(kept_np).to(DEV), dst, 2, q.to(DEV), 1, 3, scale, out, lse)
+    assert kv.kvtrim_poll_error(ctx) == 0
+    assert compare_caches(device_cache_to_host(w, dst), dst_ref)
+    o = out.cpu().numpy()
+    assert np.all(o[:, 0] == 99.0)
+    assert attn_error(o[:, 1:3], ref[:, 1:3]) <= ATTN_TOL
+    fin = np.isfinite(ref_lse[:, 1:3])
+    assert np.abs(lse.cpu().numpy()[:, 1:3][fin] - ref_lse[:, 1:3][fin]).max() <= 2e-3
 
 
 # ---------------------------------------------------------------------------------- degenerate budgets, ties
