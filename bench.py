@@ -22,7 +22,7 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs, scaled by a plain copy kernel; None until measured for this workload.
-MEASURED_TRAFFIC = {("long", "k_cmp_attn"): None, ("long", "k_cmp_copy"): None}
+MEASURED_TRAFFIC = {("long", "k_cmp_attn"): 1.0996e9 + 1.1084e9, ("long", "k_cmp_copy"): None}
 
 
 def log(*a):
@@ -51,6 +51,8 @@ def main():
     ap.add_argument("--workload", default="long", choices=["long", "llama", "vlm", "tiny"])
     ap.add_argument("--prefill", type=int, default=None, help="override the prefilled length (scaled-down run)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy, the known-size reference for rocprofv3 --pmc counters")
     ap.add_argument("--unfused", action="store_true",
                     help="run stages 3 and 4 as two calls (kvtrim_compact, kvtrim_decode_attn) instead of the fused one")
     args = ap.parse_args()
@@ -119,6 +121,14 @@ def main():
             kv.kvtrim_compact_attn(ctx, cur, keep, kept, dst, reserve, inp["q"], 0, w.n_layers, scale, out, lse)
         state["src"] = dst
         state["flip"] ^= 1
+
+    if args.pmc_calibration:                  # 2^28 floats in, 2^28 floats out, one elementwise copy kernel
+        ca = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        cb = torch.empty_like(ca)
+        cb.copy_(ca)
+        torch.cuda.synchronize()
+        del ca, cb
+        torch.cuda.empty_cache()
 
     # ---- warm-up: the first step evicts from the full prefill down to the budget
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
