@@ -229,15 +229,18 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
 }
 
 // One block per segment of the layer range: merges the partial results of its chunks, a tile
-// of COMB_TILE chunks at a time (their (m, l) pairs go through LDS so that the D-wide loads of
-// a tile are independent of each other and can all be in flight).
-constexpr int COMB_TILE = 16;
+// of COMB_TILE chunks at a time.  Phase A brings the tile's (m, l) pairs into LDS and turns
+// them into weights 2^(m - M); phase B lets every thread sum "its" (query head, d) column over
+// the tile with loads that do not depend on each other, so all of them are in flight at once.
+constexpr int COMB_TILE = 128;
+constexpr int COMB_THREADS = 512;
 template <int D>
-__global__ __launch_bounds__(ATT_THREADS) void k_att_combine(Shape sh, Workspace ws,
-                                                             const int32_t* __restrict__ chunk_prefix,
-                                                             int layer_begin, int layer_end,
-                                                             float* __restrict__ out, float* __restrict__ lse) {
-    __shared__ float s_m[COMB_TILE][8], s_l[COMB_TILE][8];
+__global__ __launch_bounds__(COMB_THREADS) void k_att_combine(Shape sh, Workspace ws,
+                                                              const int32_t* __restrict__ chunk_prefix,
+                                                              int layer_begin, int layer_end,
+                                                              float* __restrict__ out, float* __restrict__ lse) {
+    __shared__ float s_m[COMB_TILE][8], s_w[COMB_TILE][8], s_l[COMB_TILE][8];
+    __shared__ float s_M[8], s_a[8], s_L[8];
     const int G = sh.group;
     const int nl = layer_end - layer_begin;
     const int per = nl * sh.n_kv_heads;
@@ -249,58 +252,71 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_combine(Shape sh, Workspace
     const int c1 = min(chunk_prefix[seg + 1], (int)ws.max_att_chunks);
     const int64_t hq0 = ((int64_t)seq * sh.n_layers + layer) * sh.n_q_heads + (int64_t)head * G;
     const float LN2 = 0.6931471805599453f;
-    constexpr int PAIRS = (8 * D + ATT_THREADS - 1) / ATT_THREADS;   // (query, d) pairs per thread, G <= 8
-    float M[PAIRS], acc[PAIRS], lsum[PAIRS];
+    constexpr int PAIRS = (8 * D + COMB_THREADS - 1) / COMB_THREADS;   // (query head, d) pairs per thread, G <= 8
+    const int tid = threadIdx.x;
+    float acc[PAIRS];
 #pragma unroll
-    for (int p = 0; p < PAIRS; ++p) {
-        M[p] = -INFINITY;
-        acc[p] = 0.f;
-        lsum[p] = 0.f;
+    for (int p = 0; p < PAIRS; ++p) acc[p] = 0.f;
+    if (tid < 8) {
+        s_M[tid] = -INFINITY;
+        s_L[tid] = 0.f;
     }
     const size_t stride = (size_t)G * (D + 2);
     for (int t0 = c0; t0 < c1; t0 += COMB_TILE) {
         const int nt = min(COMB_TILE, c1 - t0);
         __syncthreads();
-        for (int i = threadIdx.x; i < nt * G; i += ATT_THREADS) {
+        for (int i = tid; i < nt * G; i += COMB_THREADS) {
             const float* p = ws.att_partial + (size_t)(t0 + i / G) * stride + (size_t)(i % G) * (D + 2);
             s_m[i / G][i % G] = p[0];
             s_l[i / G][i % G] = p[1];
         }
         __syncthreads();
+        if (tid < G) {                                            // running maximum and rescale factor per query head
+            float tm = s_M[tid];
+            for (int i = 0; i < nt; ++i) tm = fmaxf(tm, s_m[i][tid]);
+            const float ms = tm == -INFINITY ? 0.f : tm;
+            s_a[tid] = __builtin_amdgcn_exp2f(s_M[tid] - ms);
+            s_M[tid] = tm;
+        }
+        __syncthreads();
+        for (int i = tid; i < nt * G; i += COMB_THREADS) {
+            const float M = s_M[i % G];
+            s_w[i / G][i % G] = __builtin_amdgcn_exp2f(s_m[i / G][i % G] - (M == -INFINITY ? 0.f : M));
+        }
+        __syncthreads();
+        if (tid < G) {
+            float lv = s_L[tid] * s_a[tid];
+            for (int i = 0; i < nt; ++i) lv += s_l[i][tid] * s_w[i][tid];
+            s_L[tid] = lv;
+        }
 #pragma unroll
         for (int p = 0; p < PAIRS; ++p) {
-            const int idx = threadIdx.x + p * ATT_THREADS;
+            const int idx = tid + p * COMB_THREADS;
             if (idx >= G * D) break;
             const int g = idx / D, d = idx % D;
-            float tm = M[p];
-            for (int i = 0; i < nt; ++i) tm = fmaxf(tm, s_m[i][g]);
-            const float ms = tm == -INFINITY ? 0.f : tm;
-            const float a = __builtin_amdgcn_exp2f(M[p] - ms);
-            float x[COMB_TILE];
+            const float* base = ws.att_partial + (size_t)t0 * stride + (size_t)g * (D + 2) + 2 + d;
+            float av = acc[p] * s_a[g];
+            int i = 0;
+            for (; i + 8 <= nt; i += 8) {
+                float x[8];
 #pragma unroll
-            for (int i = 0; i < COMB_TILE; ++i)
-                x[i] = i < nt ? ws.att_partial[(size_t)(t0 + i) * stride + (size_t)g * (D + 2) + 2 + d] : 0.f;
-            float av = acc[p] * a, lv = lsum[p] * a;
+                for (int u = 0; u < 8; ++u) x[u] = base[(size_t)(i + u) * stride];
 #pragma unroll
-            for (int i = 0; i < COMB_TILE; ++i) {
-                if (i < nt) {
-                    const float w = __builtin_amdgcn_exp2f(s_m[i][g] - ms);
-                    av += x[i] * w;
-                    lv += s_l[i][g] * w;
-                }
+                for (int u = 0; u < 8; ++u) av = fmaf(x[u], s_w[i + u][g], av);
             }
+            for (; i < nt; ++i) av = fmaf(base[(size_t)i * stride], s_w[i][g], av);
             acc[p] = av;
-            lsum[p] = lv;
-            M[p] = tm;
         }
     }
+    __syncthreads();
 #pragma unroll
     for (int p = 0; p < PAIRS; ++p) {
-        const int idx = threadIdx.x + p * ATT_THREADS;
+        const int idx = tid + p * COMB_THREADS;
         if (idx >= G * D) break;
         const int g = idx / D, d = idx % D;
-        out[(hq0 + g) * D + d] = lsum[p] > 0.f ? acc[p] / lsum[p] : 0.f;
-        if (d == 0 && lse) lse[hq0 + g] = lsum[p] > 0.f ? (M[p] + __builtin_amdgcn_logf(lsum[p])) * LN2 : -INFINITY;
+        const float L = s_L[g];
+        out[(hq0 + g) * D + d] = L > 0.f ? acc[p] / L : 0.f;
+        if (d == 0 && lse) lse[hq0 + g] = L > 0.f ? (s_M[g] + __builtin_amdgcn_logf(L)) * LN2 : -INFINITY;
     }
 }
 
@@ -355,9 +371,9 @@ kvtrim_status launch_combine(kvtrim_ctx* ctx, const int32_t* chunk_prefix, int32
     const unsigned nblk = (unsigned)(sh.n_seq * (layer_end - layer_begin) * sh.n_kv_heads);
     ProfScope prof(ctx, K_ATT_COMBINE, st);
     if (sh.head_dim == 128)
-        hipLaunchKernelGGL(k_att_combine<128>, dim3(nblk), dim3(ATT_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse);
+        hipLaunchKernelGGL(k_att_combine<128>, dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse);
     else
-        hipLaunchKernelGGL(k_att_combine<64>, dim3(nblk), dim3(ATT_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse);
+        hipLaunchKernelGGL(k_att_combine<64>, dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse);
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;
 }

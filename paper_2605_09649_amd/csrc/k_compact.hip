@@ -1,50 +1,68 @@
 // Stage 3: stable stream compaction of the retained entries into a tight ragged cache.
 //
-// k_cmp_scan  one block per segment: counts the mask per 256-entry chunk, scans the counts
-//             inside the segment and derives the destination segment table from `kept`.
-// k_cmp_copy  one block per chunk: wavefront ballot/prefix ranks the survivors and the
-//             rows are streamed 16 bytes per lane, whole rows per 16 (D=128) or 8 (D=64) lanes.
+// k_cmp_scan  one block per segment: counts the mask per 128-entry chunk (wavefront ballot),
+//             scans the counts inside the segment and derives the destination segment table
+//             from `kept`.
+// k_cmp_copy  one block of 8 wavefronts per chunk: a ballot/prefix over the chunk's mask
+//             ranks the survivors; every wavefront then moves at most 16 rows in ONE batch of
+//             loads followed by one batch of stores (16 bytes per lane, whole rows per 16
+//             lanes, non-temporal) and ends.  Short-lived wavefronts measured ~10 % faster on
+//             this chip than wavefronts that loop over several batches.
 #include "kvtrim_device.h"
 
 namespace kvtrim {
 
-constexpr int CMP_THREADS = 256;
+constexpr int SCAN_THREADS = 1024;
 
-__global__ __launch_bounds__(CMP_THREADS) void k_cmp_scan(CacheView src, const uint8_t* __restrict__ keep,
-                                                          const int32_t* __restrict__ kept, CacheViewMut dst,
-                                                          int reserve, Shape sh, Workspace ws) {
+// Sums N values over the block with one pair of barriers; every thread gets every sum.
+template <int N>
+__device__ __forceinline__ void block_sum_n(int64_t (&v)[N], int64_t* lds /* [16 * N] */) {
+    const int lane = lane_id(), wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+#pragma unroll
+    for (int k = 0; k < N; ++k) v[k] = wave_sum(v[k]);
+    __syncthreads();
+    if (lane == 0) {
+#pragma unroll
+        for (int k = 0; k < N; ++k) lds[wave * N + k] = v[k];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        int64_t s = 0;
+        for (int w = 0; w < nw; ++w) s += lds[w * N + k];
+        v[k] = s;
+    }
+}
+
+__global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const uint8_t* __restrict__ keep,
+                                                           const int32_t* __restrict__ kept, CacheViewMut dst,
+                                                           int reserve, Shape sh, Workspace ws) {
     __shared__ int64_t lds64[17];
+    __shared__ int64_t lds_n[16 * 6];
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int g = blockIdx.x;
     const int nseg = sh.nseg;
 
     // chunks and destination entries of the segments before g, and the totals
-    int64_t chunks_before = 0, dst_before = 0, dst_total = 0, chunks_total = 0;
-    int64_t bad_layout = 0, bad_kept = 0;
-    for (int i = tid; i < nseg; i += CMP_THREADS) {
+    int64_t acc[6] = {0, 0, 0, 0, 0, 0};   // chunks_before, dst_before, dst_total, chunks_total, bad_layout, bad_kept
+    for (int i = tid; i < nseg; i += SCAN_THREADS) {
         const int len = src.seg_len[i];
         const int64_t st = src.seg_start[i];
         const int kp = kept[i];
-        bad_layout |= (len < 0 || st < 0 || st + len > src.cap);
-        bad_kept |= (kp < 0 || kp > len);
+        acc[4] |= (len < 0 || st < 0 || st + len > src.cap);
+        acc[5] |= (kp < 0 || kp > len);
         const int64_t nch = len > 0 ? (len + CMP_CHUNK - 1) / CMP_CHUNK : 0;
         const int64_t need = (int64_t)kp + reserve;
-        chunks_total += nch;
-        dst_total += need;
+        acc[3] += nch;
+        acc[2] += need;
         if (i < g) {
-            chunks_before += nch;
-            dst_before += need;
+            acc[0] += nch;
+            acc[1] += need;
         }
     }
-    chunks_before = block_sum<int64_t>(chunks_before, lds64);
-    dst_before = block_sum<int64_t>(dst_before, lds64);
-    dst_total = block_sum<int64_t>(dst_total, lds64);
-    chunks_total = block_sum<int64_t>(chunks_total, lds64);
-    bad_layout = block_sum<int64_t>(bad_layout, lds64);
-    bad_kept = block_sum<int64_t>(bad_kept, lds64);
-    if (bad_layout || chunks_total > ws.max_cmp_chunks) {
-        bad_layout = 1;
-    }
+    block_sum_n<6>(acc, lds_n);
+    const int64_t chunks_before = acc[0], dst_before = acc[1], dst_total = acc[2], chunks_total = acc[3];
+    const bool bad_layout = acc[4] != 0 || chunks_total > ws.max_cmp_chunks, bad_kept = acc[5] != 0;
     if (bad_layout || bad_kept || dst_total > dst.cap) {       // every block takes the same decision
         if (tid == 0) {
             atomicOr(ws.err, bad_layout ? ERR_LAYOUT : (bad_kept ? ERR_MISMATCH : ERR_CAP));
@@ -54,12 +72,13 @@ __global__ __launch_bounds__(CMP_THREADS) void k_cmp_scan(CacheView src, const u
     }
 
     const int len = src.seg_len[g];
+    const int64_t start = src.seg_start[g];
     const int nch = len > 0 ? (len + CMP_CHUNK - 1) / CMP_CHUNK : 0;
-    const uint8_t* kp = keep + src.seg_start[g];
+    const uint8_t* kp = keep + start;
     const int cbase = (int)chunks_before;
 
-    // phase 1: survivors per chunk (one wavefront per chunk, four coalesced byte loads)
-    for (int ch = wave; ch < nch; ch += CMP_THREADS / 64) {
+    // phase 1: survivors per chunk (one wavefront per chunk, two coalesced byte loads per lane)
+    for (int ch = wave; ch < nch; ch += SCAN_THREADS / 64) {
         int cnt = 0;
 #pragma unroll
         for (int r = 0; r < CMP_CHUNK / 64; ++r) {
@@ -70,7 +89,7 @@ __global__ __launch_bounds__(CMP_THREADS) void k_cmp_scan(CacheView src, const u
         if (lane == 0) {
             ws.cmp_chunk_dst[cbase + ch] = cnt;
             ChunkDesc d;
-            d.first = src.seg_start[g] + (int64_t)ch * CMP_CHUNK;
+            d.first = start + (int64_t)ch * CMP_CHUNK;
             d.n = min(CMP_CHUNK, len - ch * CMP_CHUNK);
             d.seg = g;
             ws.cmp_desc[cbase + ch] = d;
@@ -79,7 +98,7 @@ __global__ __launch_bounds__(CMP_THREADS) void k_cmp_scan(CacheView src, const u
     __syncthreads();
     // phase 2: exclusive scan of the counts inside the segment
     int64_t running = 0;
-    for (int base = 0; base < nch; base += CMP_THREADS) {
+    for (int base = 0; base < nch; base += SCAN_THREADS) {
         const int ch = base + tid;
         const int64_t v = ch < nch ? ws.cmp_chunk_dst[cbase + ch] : 0;
         int64_t tot;
@@ -98,31 +117,23 @@ __global__ __launch_bounds__(CMP_THREADS) void k_cmp_scan(CacheView src, const u
 
 typedef unsigned v4u __attribute__((ext_vector_type(4)));
 
-template <bool NT>
-__device__ __forceinline__ uint4 ld16(const uint4* p) {
-    if (NT) {
-        v4u t = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(p));
-        return make_uint4(t.x, t.y, t.z, t.w);
-    }
-    return *p;
+__device__ __forceinline__ uint4 ld16_nt(const uint4* p) {
+    v4u t = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(p));
+    return make_uint4(t.x, t.y, t.z, t.w);
 }
-template <bool NT>
-__device__ __forceinline__ void st16(uint4* p, uint4 v) {
-    if (NT) {
-        v4u t = {v.x, v.y, v.z, v.w};
-        __builtin_nontemporal_store(t, reinterpret_cast<v4u*>(p));
-    } else {
-        *p = v;
-    }
+__device__ __forceinline__ void st16_nt(uint4* p, uint4 v) {
+    v4u t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<v4u*>(p));
 }
 
-template <int D, int UNROLL, bool NT>
+template <int D>
 __global__ __launch_bounds__(CMP_THREADS) void k_cmp_copy(CacheView src, const uint8_t* __restrict__ keep,
                                                           CacheViewMut dst, Shape sh, Workspace ws) {
-    constexpr int VPR = D / 8;            // 16-byte vectors per row
-    constexpr int RPI = 64 / VPR;         // rows moved by one wavefront instruction
-    __shared__ int wave_cnt[4];
-    __shared__ int list[4][64];
+    constexpr int VPR = D / 8;                    // 16-byte vectors per row
+    constexpr int RPI = 64 / VPR;                 // rows moved by one wavefront instruction
+    constexpr int BATCH = CMP_WAVE_ROWS / RPI;    // instructions per wavefront: 4 (D=128) or 2 (D=64)
+    __shared__ int wave_cnt[CMP_CHUNK / 64];
+    __shared__ int list[CMP_CHUNK];
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     if (__hip_atomic_load(ws.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
     const int total = ws.cmp_chunk_prefix[sh.nseg];
@@ -130,44 +141,51 @@ __global__ __launch_bounds__(CMP_THREADS) void k_cmp_copy(CacheView src, const u
     if (ch >= total) return;
     const ChunkDesc d = ws.cmp_desc[ch];
     const int64_t sbase = d.first;                                // first source entry of the chunk
-    const bool flag = tid < d.n && keep[sbase + tid] != 0;
-    const uint64_t mask = __ballot(flag);
-    const int rank = mbcnt(mask);
-    const int cnt = __popcll(mask);
-    if (lane == 0) wave_cnt[wave] = cnt;
-    if (flag) list[wave][rank] = tid;
+    const int64_t dbase = ws.cmp_chunk_dst[ch];                   // first destination entry of its survivors
+    // the first CMP_CHUNK threads rank the survivors
+    int rank = 0;
+    bool flag = false;
+    if (tid < CMP_CHUNK) {
+        flag = tid < d.n && keep[sbase + tid] != 0;
+        const uint64_t mask = __ballot(flag);
+        rank = mbcnt(mask);
+        if (lane == 0) wave_cnt[wave] = __popcll(mask);
+    }
     __syncthreads();
-    int wbase = 0;
-    for (int w = 0; w < wave; ++w) wbase += wave_cnt[w];
-    const int64_t dbase = ws.cmp_chunk_dst[ch] + wbase;           // first destination entry of this wavefront
+    int cnt = 0;
+#pragma unroll
+    for (int w = 0; w < CMP_CHUNK / 64; ++w) {
+        if (w < wave && tid < CMP_CHUNK) rank += wave_cnt[w];
+        cnt += wave_cnt[w];
+    }
     if (flag) {
+        list[rank] = tid;
         dst.log_beta[dbase + rank] = src.log_beta[sbase + tid];
         dst.pos[dbase + rank] = src.pos[sbase + tid];
     }
+    __syncthreads();
+    const int r0 = wave * CMP_WAVE_ROWS;                          // this wavefront's rows of the survivor list
+    if (r0 >= cnt) return;
     const uint4* sk = reinterpret_cast<const uint4*>(src.k);
     const uint4* sv = reinterpret_cast<const uint4*>(src.v);
     uint4* dk = reinterpret_cast<uint4*>(dst.k);
     uint4* dv = reinterpret_cast<uint4*>(dst.v);
     const int sub = lane / VPR, col = lane % VPR;
-    for (int r0 = 0; r0 < cnt; r0 += RPI * UNROLL) {
-        uint4 kk[UNROLL], vv[UNROLL];
+    uint4 kk[BATCH], vv[BATCH];
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const int r = r0 + u * RPI + sub;
-            if (r < cnt) {
-                const int64_t se = (sbase + list[wave][r]) * VPR + col;
-                kk[u] = ld16<NT>(sk + se);
-                vv[u] = ld16<NT>(sv + se);
-            }
-        }
+    for (int u = 0; u < BATCH; ++u) {
+        const int r = min(r0 + u * RPI + sub, cnt - 1);           // clamped: loads stay on live rows
+        const int64_t se = (sbase + list[r]) * VPR + col;
+        kk[u] = ld16_nt(sk + se);
+        vv[u] = ld16_nt(sv + se);
+    }
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const int r = r0 + u * RPI + sub;
-            if (r < cnt) {
-                const int64_t de = (dbase + r) * VPR + col;
-                st16<NT>(dk + de, kk[u]);
-                st16<NT>(dv + de, vv[u]);
-            }
+    for (int u = 0; u < BATCH; ++u) {
+        const int r = r0 + u * RPI + sub;
+        if (r < cnt) {
+            const int64_t de = (dbase + r) * VPR + col;
+            st16_nt(dk + de, kk[u]);
+            st16_nt(dv + de, vv[u]);
         }
     }
 }
@@ -175,7 +193,7 @@ __global__ __launch_bounds__(CMP_THREADS) void k_cmp_copy(CacheView src, const u
 void launch_cmp_scan(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const int32_t* kept,
                      const CacheViewMut& dst, int32_t reserve, hipStream_t st) {
     ProfScope prof(ctx, K_CMP_SCAN, st);
-    hipLaunchKernelGGL(k_cmp_scan, dim3(ctx->shape.nseg), dim3(CMP_THREADS), 0, st, src, keep, kept, dst, reserve,
+    hipLaunchKernelGGL(k_cmp_scan, dim3(ctx->shape.nseg), dim3(SCAN_THREADS), 0, st, src, keep, kept, dst, reserve,
                        ctx->shape, ctx->ws);
 }
 
@@ -188,20 +206,10 @@ kvtrim_status launch_compact(kvtrim_ctx* ctx, const CacheView& src, const uint8_
     if (max_chunks > 0) {
         ProfScope prof(ctx, K_CMP_COPY, st);
         const dim3 grid((unsigned)max_chunks), block(CMP_THREADS);
-#define KVTRIM_COPY(D_, U_, NT_) hipLaunchKernelGGL((k_cmp_copy<D_, U_, NT_>), grid, block, 0, st, src, keep, dst, sh, ws)
-#define KVTRIM_COPY_U(D_, NT_)                                       \
-    switch (ctx->cmp_unroll) {                                       \
-        case 1: KVTRIM_COPY(D_, 1, NT_); break;                      \
-        case 2: KVTRIM_COPY(D_, 2, NT_); break;                      \
-        default: KVTRIM_COPY(D_, 4, NT_); break;                     \
-    }
-        if (sh.head_dim == 128) {
-            if (ctx->cmp_nt) { KVTRIM_COPY_U(128, true) } else { KVTRIM_COPY_U(128, false) }
-        } else {
-            if (ctx->cmp_nt) { KVTRIM_COPY_U(64, true) } else { KVTRIM_COPY_U(64, false) }
-        }
-#undef KVTRIM_COPY_U
-#undef KVTRIM_COPY
+        if (sh.head_dim == 128)
+            hipLaunchKernelGGL(k_cmp_copy<128>, grid, block, 0, st, src, keep, dst, sh, ws);
+        else
+            hipLaunchKernelGGL(k_cmp_copy<64>, grid, block, 0, st, src, keep, dst, sh, ws);
     }
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;

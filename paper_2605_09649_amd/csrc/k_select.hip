@@ -184,11 +184,10 @@ __global__ __launch_bounds__(CNT_THREADS) void k_sel_count(const float* __restri
     if (ws.done[4] == 0) return;                                  // uniform over the grid
     const int tid = threadIdx.x;
     const int total = ws.sel_chunk_prefix[sh.nseg];
-    const int ch = blockIdx.x;
-    if (ch < total) {
+    for (int ch = blockIdx.x; ch < total; ch += gridDim.x) {
         const ChunkDesc d = ws.sel_desc[ch];
         const SelState st = ws.sel[d.seg / sh.segs_per_seq];
-        if (st.need_rank) {
+        if (st.need_rank) {                                       // uniform over the block
             int gt = 0, eq = 0;
             for (int j = tid; j < d.n; j += CNT_THREADS) {
                 const uint32_t key = key_of_score(score[d.first + j]);
@@ -310,7 +309,7 @@ kvtrim_status launch_select(kvtrim_ctx* ctx, const CacheView& c, const float* sc
     { ProfScope prof(ctx, K_SEL_HIST2, st);
       hipLaunchKernelGGL(k_sel_hist<2>, dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, thr); }
     { ProfScope prof(ctx, K_SEL_COUNT, st);
-      hipLaunchKernelGGL(k_sel_count, dim3(n_chunk_blocks), dim3(CNT_THREADS), 0, st, score, sh, ws, kept); }
+      hipLaunchKernelGGL(k_sel_count, dim3(n_chunk_blocks < 256 ? n_chunk_blocks : 256), dim3(CNT_THREADS), 0, st, score, sh, ws, kept); }
     { ProfScope prof(ctx, K_SEL_MASK, st);
       hipLaunchKernelGGL(k_sel_mask, dim3(n_chunk_blocks), dim3(SEL_THREADS), 0, st, score, sh, ws, keep, kept); }
     KVTRIM_HIP(ctx, hipGetLastError());

@@ -52,7 +52,9 @@ static Layout layout_of(const kvtrim_config* c) {
     l.max_cmp_chunks = c->max_entries / CMP_CHUNK + nseg;
     // the attention chunk grows with the capacity (att_chunk_for) so that at most 16384 full
     // chunks plus one ragged tail per segment ever exist
-    const int64_t full = c->max_entries / 256 < 16384 ? c->max_entries / 256 : 16384;
+    // (the fused stage 3+4 kernel also writes one partial result per 128-entry compaction chunk;
+    // it is used for caches of up to 32768 such chunks, larger ones take the two-call path)
+    const int64_t full = c->max_entries / CMP_CHUNK < 32768 ? c->max_entries / CMP_CHUNK : 32768;
     const int64_t att = full + nseg + 1;
     l.max_att_chunks = att;
     size_t cur = 0;
@@ -141,10 +143,6 @@ kvtrim_status kvtrim_create(kvtrim_ctx** out, const kvtrim_config* cfg) {
         const int v = atoi(e);
         if (v >= 256 && v <= 65536 && v % 64 == 0) ctx->att_chunk_min = v;
     }
-    ctx->cmp_unroll = 4;
-    ctx->cmp_nt = 1;
-    if (const char* e = getenv("KVTRIM_CMP_UNROLL")) ctx->cmp_unroll = atoi(e);
-    if (const char* e = getenv("KVTRIM_CMP_NT")) ctx->cmp_nt = atoi(e) != 0;
     const Layout l = layout_of(cfg);
     ctx->ws_bytes = l.total;
     if (hipGetDevice(&ctx->device) != hipSuccess || hipMalloc(&ctx->ws_base, l.total) != hipSuccess) {

@@ -9,7 +9,9 @@ namespace kvtrim {
 
 // Chunk sizes (entries of one segment handled as a unit).
 constexpr int SEL_CHUNK = 2048;      // selection: 256 threads x 8 entries
-constexpr int CMP_CHUNK = 256;       // compaction: 256 threads, 64 entries per wave
+constexpr int CMP_CHUNK = 128;       // compaction: entries per block
+constexpr int CMP_WAVE_ROWS = 16;    // rows a wavefront moves (one batch of loads, one of stores)
+constexpr int CMP_THREADS = CMP_CHUNK / CMP_WAVE_ROWS * 64;   // 512: one wavefront per 16 survivors
 constexpr int RADIX_BITS0 = 11, RADIX_BITS1 = 11, RADIX_BITS2 = 10;
 constexpr int RADIX_BINS = 2048;     // bins of the widest pass
 constexpr int HIST_REPLICAS = 8;     // copies of the merged histogram (spreads the device-scope atomics)
@@ -103,7 +105,6 @@ struct kvtrim_ctx {
     int32_t* err_host;           // pinned mirror of the device flag
     int device;
     int att_chunk_min;           // rows per attention chunk (multiple of 64, >= 256); KVTRIM_ATT_CHUNK overrides
-    int cmp_unroll, cmp_nt;      // row-copy shape of the compaction (KVTRIM_CMP_UNROLL, KVTRIM_CMP_NT override)
     char last_error[256];
     // instrumentation
     uint32_t prof_mask;
