@@ -16,24 +16,32 @@ namespace kvtrim {
 constexpr int SEL_THREADS = 256;      // mask kernel: one chunk per block, 8 entries per thread
 constexpr int CNT_THREADS = 1024;
 constexpr int HIST_THREADS = 1024;    // histogram passes: few fat blocks, so that few device-scope
-constexpr int HIST_BLOCKS = 256;      // atomics meet on one address when the LDS histograms are merged
+constexpr int HIST_BLOCKS = HIST_BLOCKS_MAX;   // atomics meet on one address when the LDS histograms are merged
                                       // (the merged histogram is also kept in HIST_REPLICAS copies)
 constexpr int PLAN_ZERO_BLOCKS = 8;   // extra blocks of the plan kernel that clear the histograms
-constexpr int SEL_SHIFT = 11;         // log2(SEL_CHUNK)
-static_assert((1 << SEL_SHIFT) == SEL_CHUNK, "SEL_SHIFT out of step with SEL_CHUNK");
 
 __global__ __launch_bounds__(1024) void k_sel_plan(CacheView c, Shape sh, const int64_t* __restrict__ budget,
-                                                   Workspace ws, int32_t* __restrict__ kept_out) {
+                                                   Workspace ws, int32_t* __restrict__ kept_out, int hist_blocks) {
     if (blockIdx.x > 0) {                      // clear the (replicated) histograms of the three passes
         const int n = 3 * HIST_REPLICAS * sh.n_seq * RADIX_BINS;
         for (int i = (blockIdx.x - 1) * blockDim.x + threadIdx.x; i < n; i += (gridDim.x - 1) * blockDim.x)
             ws.hist[i] = 0;
         return;
     }
-    for (int i = threadIdx.x; i < 8; i += blockDim.x) ws.done[i] = 0;
+    for (int i = threadIdx.x; i < DONE_WORDS; i += blockDim.x) ws.done[i] = 0;
     for (int g = threadIdx.x; g < sh.nseg; g += blockDim.x) kept_out[g] = 0;
-    build_chunk_table(c.seg_len, c.seg_start, sh.nseg, [](int) { return true; }, SEL_CHUNK, c.cap,
-                      ws.sel_chunk_prefix, ws.sel_desc, ws.max_sel_chunks, ws.sel_entry_prefix, ws.err);
+    const int total = build_chunk_table(c.seg_len, c.seg_start, sh.nseg, [](int) { return true; }, SEL_CHUNK, c.cap,
+                                        ws.sel_chunk_prefix, ws.sel_desc, ws.max_sel_chunks, ws.sel_entry_prefix, ws.err);
+    if ((int)threadIdx.x < hist_blocks) {                         // chunk range of every histogram block
+        const int cpb = (total + hist_blocks - 1) / hist_blocks;
+        const int c0 = min(total, (int)threadIdx.x * cpb), c1 = min(total, c0 + cpb);
+        int4 r = make_int4(c0, c1, 0, -1);
+        if (c0 < c1) {
+            r.z = ws.sel_desc[c0].seg / sh.segs_per_seq;
+            r.w = ws.sel_desc[c1 - 1].seg / sh.segs_per_seq;
+        }
+        ws.sel_blk[threadIdx.x] = r;
+    }
     for (int seq = threadIdx.x; seq < sh.n_seq; seq += blockDim.x) {
         const int64_t n = ws.sel_entry_prefix[(seq + 1) * sh.segs_per_seq] - ws.sel_entry_prefix[seq * sh.segs_per_seq];
         int64_t b = budget[seq];
@@ -51,18 +59,18 @@ __global__ __launch_bounds__(1024) void k_sel_plan(CacheView c, Shape sh, const 
     }
 }
 
-template <int PASS>
-__device__ __forceinline__ bool digit_of(uint32_t key, uint32_t prefix, int* bin) {
-    if (PASS == 0) {
-        *bin = key >> 21;
-        return true;
-    } else if (PASS == 1) {
-        *bin = (key >> 10) & 2047;
-        return (key >> 21) == prefix;
-    } else {
-        *bin = key & 1023;
-        return (key >> 10) == prefix;
-    }
+// "Last block done" detection, called by one thread per block after the block's results are
+// written.  Device-scope atomics on ONE address are served one after the other (tens of
+// nanoseconds each), so 256 blocks do not meet on one counter: 16 group counters first, then the
+// last block of each group on the top-level counter.  counters: [0] top level, [1..16] groups.
+__device__ __forceinline__ bool arrive_last(uint32_t* counters) {
+    __threadfence();
+    const unsigned grp = blockIdx.x & 15u;
+    const unsigned gsize = (gridDim.x - grp + 15u) / 16u;        // blocks with this group number
+    if (atomicAdd(&counters[1 + grp], 1u) != gsize - 1) return false;
+    __threadfence();
+    const unsigned ngroups = gridDim.x < 16u ? gridDim.x : 16u;
+    return atomicAdd(&counters[0], 1u) == ngroups - 1;
 }
 
 // Histogram of the next digit over the entries whose higher digits equal the prefix found so
@@ -74,34 +82,41 @@ template <int PASS>
 __global__ __launch_bounds__(HIST_THREADS) void k_sel_hist(const float* __restrict__ score, Shape sh,
                                                            Workspace ws, uint32_t* __restrict__ thr_out) {
     constexpr int NB = PASS == 2 ? 1024 : 2048;
+    constexpr int HIST_TILE = 64;
     __shared__ uint32_t h[NB];
+    __shared__ ChunkDesc s_desc[HIST_TILE];
     __shared__ int64_t lds64[17];
     __shared__ int is_last;
     const int tid = threadIdx.x;
-    const int total = ws.sel_chunk_prefix[sh.nseg];
-    const int cpb = (total + gridDim.x - 1) / gridDim.x;
-    const int c0 = min(total, (int)blockIdx.x * cpb), c1 = min(total, c0 + cpb);
+    const int4 rng = ws.sel_blk[blockIdx.x];
+    const int c0 = rng.x, c1 = rng.y;
     uint32_t* hist_pass = ws.hist + (size_t)PASS * HIST_REPLICAS * sh.n_seq * RADIX_BINS;
     uint32_t* hist = hist_pass + (size_t)(blockIdx.x % HIST_REPLICAS) * sh.n_seq * RADIX_BINS;
 
     if (c0 < c1) {
         for (int i = tid; i < NB; i += HIST_THREADS) h[i] = 0;
-        const int seq_lo = ws.sel_desc[c0].seg / sh.segs_per_seq;
-        const int seq_hi = ws.sel_desc[c1 - 1].seg / sh.segs_per_seq;
+        const int seq_lo = rng.z, seq_hi = rng.w;
         for (int seq = seq_lo; seq <= seq_hi; ++seq) {
             const int a = max(c0, ws.sel_chunk_prefix[seq * sh.segs_per_seq]);
             const int b = min(c1, ws.sel_chunk_prefix[(seq + 1) * sh.segs_per_seq]);
             if (a >= b) continue;
             const uint32_t prefix = ws.sel[seq].prefix;
             if (ws.sel[seq].keep_none) continue;
-            __syncthreads();
-#pragma unroll 4
-            for (int64_t slot = ((int64_t)a << SEL_SHIFT) + tid; slot < ((int64_t)b << SEL_SHIFT); slot += HIST_THREADS) {
-                const ChunkDesc d = ws.sel_desc[slot >> SEL_SHIFT];
-                const int j = (int)(slot & (SEL_CHUNK - 1));
-                if (j < d.n) {
-                    int bin;
-                    if (digit_of<PASS>(key_of_score(score[d.first + j]), prefix, &bin)) atomicAdd(&h[bin], 1u);
+            // the descriptors of a tile of chunks go through LDS so that the score loads of a
+            // thread do not depend on anything loaded inside the loop and are all in flight at once
+            for (int t0 = a; t0 < b; t0 += HIST_TILE) {
+                const int nt = min(HIST_TILE, b - t0);
+                __syncthreads();
+                if (tid < nt) s_desc[tid] = ws.sel_desc[t0 + tid];
+                __syncthreads();
+#pragma unroll 8
+                for (int slot = tid; slot < (nt << SEL_SHIFT); slot += HIST_THREADS) {
+                    const ChunkDesc d = s_desc[slot >> SEL_SHIFT];
+                    const int j = slot & (SEL_CHUNK - 1);
+                    if (j < d.n) {
+                        int bin;
+                        if (digit_of<PASS>(key_of_score(score[d.first + j]), prefix, &bin)) atomicAdd(&h[bin], 1u);
+                    }
                 }
             }
             __syncthreads();
@@ -115,10 +130,7 @@ __global__ __launch_bounds__(HIST_THREADS) void k_sel_hist(const float* __restri
         }
     }
     __syncthreads();
-    if (tid == 0) {
-        __threadfence();
-        is_last = atomicAdd(&ws.done[PASS], 1u) == gridDim.x - 1;
-    }
+    if (tid == 0) is_last = arrive_last(ws.done + 32 * PASS);
     __syncthreads();
     if (!is_last) return;
     __threadfence();
@@ -139,9 +151,8 @@ __global__ __launch_bounds__(HIST_THREADS) void k_sel_hist(const float* __restri
             const int bin = NB - 1 - (tid * PER + i);
             uint32_t v = 0;
 #pragma unroll
-            for (int r = 0; r < HIST_REPLICAS; ++r)
-                v += __hip_atomic_load(&hist_pass[((size_t)r * sh.n_seq + seq) * RADIX_BINS + bin], __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_AGENT);
+            for (int r = 0; r < HIST_REPLICAS; ++r)      // plain loads: the fence above made the other blocks' sums visible
+                v += hist_pass[((size_t)r * sh.n_seq + seq) * RADIX_BINS + bin];
             cnt[i] = v;
             mine += v;
         }
@@ -159,7 +170,7 @@ __global__ __launch_bounds__(HIST_THREADS) void k_sel_hist(const float* __restri
                         st.thr_key = st.prefix;
                         st.tie_quota = st.rank;
                         st.need_rank = st.rank < (int64_t)cnt[i];   // fewer survive than tie at the threshold
-                        if (st.need_rank) atomicOr((int*)&ws.done[4], 1);
+                        if (st.need_rank) atomicOr((int*)&ws.done[127], 1);
                         if (thr_out) thr_out[seq] = st.thr_key;
                     }
                     ws.sel[seq] = st;
@@ -181,7 +192,7 @@ __global__ __launch_bounds__(CNT_THREADS) void k_sel_count(const float* __restri
     __shared__ int64_t lds64[17];
     __shared__ int32_t lds32[17];
     __shared__ int is_last;
-    if (ws.done[4] == 0) return;                                  // uniform over the grid
+    if (ws.done[127] == 0) return;                                // uniform over the grid
     const int tid = threadIdx.x;
     const int total = ws.sel_chunk_prefix[sh.nseg];
     for (int ch = blockIdx.x; ch < total; ch += gridDim.x) {
@@ -203,10 +214,7 @@ __global__ __launch_bounds__(CNT_THREADS) void k_sel_count(const float* __restri
         }
     }
     __syncthreads();
-    if (tid == 0) {
-        __threadfence();
-        is_last = atomicAdd(&ws.done[3], 1u) == gridDim.x - 1;
-    }
+    if (tid == 0) is_last = arrive_last(ws.done + 32 * 3);
     __syncthreads();
     if (!is_last) return;
     __threadfence();
@@ -301,7 +309,7 @@ kvtrim_status launch_select(kvtrim_ctx* ctx, const CacheView& c, const float* sc
     const int n_chunk_blocks = (int)max_chunks;
     const int hist_blocks = (int)(max_chunks < HIST_BLOCKS ? (max_chunks < 1 ? 1 : max_chunks) : HIST_BLOCKS);
     { ProfScope prof(ctx, K_SEL_PLAN, st);
-      hipLaunchKernelGGL(k_sel_plan, dim3(1 + PLAN_ZERO_BLOCKS), dim3(1024), 0, st, c, sh, budget, ws, kept); }
+      hipLaunchKernelGGL(k_sel_plan, dim3(1 + PLAN_ZERO_BLOCKS), dim3(1024), 0, st, c, sh, budget, ws, kept, hist_blocks); }
     { ProfScope prof(ctx, K_SEL_HIST0, st);
       hipLaunchKernelGGL(k_sel_hist<0>, dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, thr); }
     { ProfScope prof(ctx, K_SEL_HIST1, st);

@@ -62,7 +62,7 @@ static Layout layout_of(const kvtrim_config* c) {
     l.off[1] = bump(cur, l.max_sel_chunks * sizeof(ChunkDesc));                // sel_desc
     l.off[2] = bump(cur, (size_t)3 * HIST_REPLICAS * c->n_seq * RADIX_BINS * sizeof(uint32_t)); // hist
     l.off[3] = bump(cur, (size_t)c->n_seq * sizeof(SelState));                 // sel
-    l.off[4] = bump(cur, 8 * sizeof(uint32_t));                                // done
+    l.off[4] = bump(cur, DONE_WORDS * sizeof(uint32_t));                       // done
     l.off[5] = bump(cur, l.max_sel_chunks * sizeof(int32_t));                  // chunk_eq
     l.off[6] = bump(cur, l.max_sel_chunks * sizeof(int64_t));                  // chunk_tie_base
     l.off[7] = bump(cur, (nseg + 1) * sizeof(int32_t));                        // cmp_chunk_prefix
@@ -73,6 +73,7 @@ static Layout layout_of(const kvtrim_config* c) {
     l.off[12] = bump(cur, (size_t)l.max_att_chunks * G * (c->head_dim + 2) * sizeof(float)); // att_partial
     l.off[13] = bump(cur, 256);                                                // err
     l.off[14] = bump(cur, (nseg + 1) * sizeof(int64_t));                       // sel_entry_prefix
+    l.off[15] = bump(cur, HIST_BLOCKS_MAX * sizeof(int4));                     // sel_blk
     l.total = (cur + 255) & ~(size_t)255;
     return l;
 }
@@ -175,6 +176,7 @@ kvtrim_status kvtrim_create(kvtrim_ctx** out, const kvtrim_config* cfg) {
     w.att_partial = (float*)(b + l.off[12]);
     w.err = (int32_t*)(b + l.off[13]);
     w.sel_entry_prefix = (int64_t*)(b + l.off[14]);
+    w.sel_blk = (int4*)(b + l.off[15]);
     w.max_sel_chunks = l.max_sel_chunks;
     w.max_cmp_chunks = l.max_cmp_chunks;
     w.max_att_chunks = l.max_att_chunks;

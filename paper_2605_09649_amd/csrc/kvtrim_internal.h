@@ -8,12 +8,16 @@
 namespace kvtrim {
 
 // Chunk sizes (entries of one segment handled as a unit).
-constexpr int SEL_CHUNK = 2048;      // selection: 256 threads x 8 entries
+constexpr int SEL_CHUNK = 2048;      // selection: entries per chunk
+constexpr int SEL_SHIFT = 11;        // log2(SEL_CHUNK)
+static_assert((1 << SEL_SHIFT) == SEL_CHUNK, "SEL_SHIFT out of step with SEL_CHUNK");
 constexpr int CMP_CHUNK = 128;       // compaction: entries per block
 constexpr int CMP_WAVE_ROWS = 16;    // rows a wavefront moves (one batch of loads, one of stores)
 constexpr int CMP_THREADS = CMP_CHUNK / CMP_WAVE_ROWS * 64;   // 512: one wavefront per 16 survivors
 constexpr int RADIX_BITS0 = 11, RADIX_BITS1 = 11, RADIX_BITS2 = 10;
 constexpr int RADIX_BINS = 2048;     // bins of the widest pass
+constexpr int HIST_BLOCKS_MAX = 256; // blocks of a histogram pass (few and fat: see k_select.hip)
+constexpr int DONE_WORDS = 128;      // 4 sets of 32 counters (three histogram passes, the tie count)
 constexpr int HIST_REPLICAS = 8;     // copies of the merged histogram (spreads the device-scope atomics)
 
 constexpr int ERR_CAP = 1;           // bits of the sticky device flag
@@ -69,9 +73,10 @@ struct Workspace {
     int32_t* sel_chunk_prefix;   // [nseg+1] first chunk of each segment
     ChunkDesc* sel_desc;         // [max_sel_chunks]
     int64_t* sel_entry_prefix;   // [nseg+1] entries before each segment
+    int4* sel_blk;               // [HIST_BLOCKS_MAX] per histogram block: first chunk, end chunk, first and last sequence
     uint32_t* hist;              // [3][HIST_REPLICAS][n_seq][RADIX_BINS]
     SelState* sel;               // [n_seq]
-    uint32_t* done;              // [8] "last block" counters
+    uint32_t* done;              // [DONE_WORDS] "last block" counters: per pass one top-level and 16 group counters
     int32_t* chunk_eq;           // [max_sel_chunks] entries equal to the threshold
     int64_t* chunk_tie_base;     // [max_sel_chunks] ties of the sequence before the chunk
     // compaction
@@ -164,6 +169,22 @@ struct ProfScope {
 };
 
 // ---- device helpers --------------------------------------------------------------------
+// Digit of pass PASS (11 + 11 + 10 bits, most significant first) and whether the higher digits
+// of the key equal the prefix fixed so far.
+template <int PASS>
+__device__ __forceinline__ bool digit_of(uint32_t key, uint32_t prefix, int* bin) {
+    if (PASS == 0) {
+        *bin = key >> 21;
+        return true;
+    } else if (PASS == 1) {
+        *bin = (key >> 10) & 2047;
+        return (key >> 21) == prefix;
+    } else {
+        *bin = key & 1023;
+        return (key >> 10) == prefix;
+    }
+}
+
 __device__ __forceinline__ uint32_t key_of_score(float s) {
     uint32_t u = __float_as_uint(s);
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
