@@ -1,0 +1,162 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+long (32 layers x 8 KV heads, 131072 prefilled, B = 2,097,152):
+  - the first eviction (33.5 M candidates): selection compared whole against the oracle (only
+    metadata is needed on the host); compaction and attention on sampled segments;
+  - steady-state steps (2.1 M candidates, fused stage 3+4 path): compared whole.
+llama (32768 prefilled), vlm (two sequences, G = 7) and a 16-sequence multi-turn cache: whole.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import kvtrim_inputs as ki
+import oracle
+import paper_2605_09649_amd as kv
+from harness import attn_error, compare_caches, device_cache_to_host, run_steps_both
+from helpers import bf16_bits, shape_of
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+ATTN_TOL = 5e-3
+
+
+def check(results):
+    for i, r in enumerate(results):
+        assert r["status"] == 0, (i, r)
+        assert r["score_equal"] and r["keep_equal"] and r["cache_equal"], (i, r)
+        assert r["attn_err"] <= ATTN_TOL and r["lse_err"] <= 2e-3 and r["lse_inf_equal"], (i, r)
+
+
+def test_llama_32k_whole():
+    w = ki.workload("llama")
+    pre = {k: (v.cpu() if torch.is_tensor(v) else v) for k, v in ki.prefill_cache(w, device=DEV).items()}
+    check(run_steps_both(w, steps=3, budget=w.budget, device=DEV, cache_dict=pre, now0=[t - 1 for t in w.prefill],
+                         fused=True))
+
+
+def test_vlm_two_sequences_whole():
+    w = ki.workload("vlm")
+    pre = {k: (v.cpu() if torch.is_tensor(v) else v) for k, v in ki.prefill_cache(w, device=DEV).items()}
+    check(run_steps_both(w, steps=3, budget=w.budget, device=DEV, cache_dict=pre, now0=[t - 1 for t in w.prefill],
+                         fused=True))
+
+
+def test_multiturn_sixteen_sequences():
+    w = ki.workload("multiturn", prefill=4096)
+    pre = {k: (v.cpu() if torch.is_tensor(v) else v) for k, v in ki.prefill_cache(w, device=DEV).items()}
+    check(run_steps_both(w, steps=2, budget=w.budget, device=DEV, cache_dict=pre, now0=[t - 1 for t in w.prefill],
+                         fused=True))
+
+
+def test_long_128k_first_eviction_and_steady_state():
+    w = ki.workload("long")
+    sh = shape_of(w)
+    reserve = 1
+    pre = ki.prefill_cache(w, reserve=reserve, device=DEV)
+    src = kv.Cache.from_dict(pre, DEV)
+    B = w.budget[0]
+    dst_cap = B + w.nseg * reserve + 8
+    ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, src.cap)
+    spare = [kv.Cache.empty(w.nseg, w.head_dim, dst_cap, DEV) for _ in range(2)]
+    score = torch.zeros(src.cap, dtype=torch.float32, device=DEV)
+    keep = torch.zeros(src.cap, dtype=torch.uint8, device=DEV)
+    kept = torch.zeros(w.nseg, dtype=torch.int32, device=DEV)
+    thr = torch.zeros(1, dtype=torch.int32, device=DEV)
+    budget = torch.tensor([B], dtype=torch.int64, device=DEV)
+    out = torch.zeros(1, w.n_layers, w.n_q_heads, w.head_dim, dtype=torch.float32, device=DEV)
+    lse = torch.zeros(1, w.n_layers, w.n_q_heads, dtype=torch.float32, device=DEV)
+    scale = 1.0 / math.sqrt(w.head_dim)
+    G, D = w.group, w.head_dim
+
+    # ---- first step: 33.5 M candidates -> 2.1 M survivors
+    inp = ki.decode_inputs(w, 0, device=DEV)
+    now = np.array([w.prefill[0]], np.int32)
+    pos_new = np.full(w.nseg, now[0], np.int32)
+    kv.kvtrim_append(ctx, src, inp["k_new"], inp["v_new"], inp["log_beta_new"], torch.from_numpy(pos_new).to(DEV), 1)
+    kv.kvtrim_score(ctx, src, torch.from_numpy(now).to(DEV), score)
+    kv.kvtrim_select_global(ctx, src, score, budget, keep, kept, thr)
+    kv.kvtrim_compact_attn(ctx, src, keep, kept, spare[0], reserve, inp["q"], 0, w.n_layers, scale, out, lse)
+    assert kv.kvtrim_poll_error(ctx) == 0
+
+    # oracle selection on the metadata alone (no K/V rows on the host)
+    empty = np.zeros((0, D), np.uint16)
+    meta = oracle.HostCache.from_arrays(sh, empty, empty, src.log_beta.cpu().numpy(), src.pos.cpu().numpy(),
+                                        src.seg_start.cpu().numpy(), src.seg_len.cpu().numpy())
+    score_ref = oracle.score(meta, now)
+    keep_ref, kept_ref, thr_ref = oracle.select(meta, score_ref, np.array([B], np.int64))
+    live = np.zeros(meta.cap, bool)
+    for s, n in zip(meta.seg_start, meta.seg_len):
+        live[s:s + n] = True
+    assert np.array_equal(score.cpu().numpy()[live].view(np.uint32), score_ref[live].view(np.uint32))
+    keep_gpu = keep.cpu().numpy()
+    assert np.array_equal(keep_gpu[live], keep_ref[live])
+    assert np.array_equal(kept.cpu().numpy(), kept_ref)
+    assert thr.cpu().numpy().view(np.uint32)[0] == thr_ref[0]
+    assert kept_ref.sum() == B
+
+    # compaction: segment table and metadata whole, rows on sampled segments
+    dst = spare[0]
+    exp_start = np.concatenate([[0], np.cumsum(kept_ref.astype(np.int64) + reserve)[:-1]])
+    assert np.array_equal(dst.seg_start.cpu().numpy(), exp_start)
+    assert np.array_equal(dst.seg_len.cpu().numpy(), kept_ref)
+    sel = keep_ref.astype(bool) & live
+    dlive = np.zeros(dst.cap, bool)
+    for s, n in zip(exp_start, kept_ref):
+        dlive[s:s + n] = True
+    assert np.array_equal(dst.log_beta.cpu().numpy()[dlive].view(np.uint32), meta.log_beta[sel].view(np.uint32))
+    assert np.array_equal(dst.pos.cpu().numpy()[dlive], meta.pos[sel])
+    rng = np.random.default_rng(7)
+    sample = sorted(rng.choice(w.nseg, 8, replace=False).tolist() + [int(np.argmax(kept_ref)), int(np.argmin(kept_ref))])
+    small_shape = oracle.Shape(1, 1, len(sample), len(sample) * G, D)
+    rows_k, rows_v, lens, qs, out_rows = [], [], [], [], []
+    q_host = bf16_bits(inp["q"]).reshape(w.n_layers, w.n_q_heads, D)
+    out_gpu = out.cpu().numpy()[0]
+    for g in sample:
+        s0, n = int(meta.seg_start[g]), int(meta.seg_len[g])
+        m = torch.from_numpy(keep_ref[s0:s0 + n].astype(bool)).to(DEV)
+        ks = bf16_bits(src.k[s0:s0 + n][m])
+        vs = bf16_bits(src.v[s0:s0 + n][m])
+        d0, dn = int(exp_start[g]), int(kept_ref[g])
+        assert np.array_equal(bf16_bits(dst.k[d0:d0 + dn]), ks), g
+        assert np.array_equal(bf16_bits(dst.v[d0:d0 + dn]), vs), g
+        rows_k.append(ks)
+        rows_v.append(vs)
+        lens.append(dn)
+        layer, head = divmod(g, w.n_kv_heads)
+        qs.append(q_host[layer, head * G:(head + 1) * G])
+        out_rows.append(out_gpu[layer, head * G:(head + 1) * G])
+    starts = np.concatenate([[0], np.cumsum(lens)[:-1]]).astype(np.int64)
+    n_tot = int(np.sum(lens))
+    small = oracle.HostCache.from_arrays(small_shape, np.concatenate(rows_k), np.concatenate(rows_v),
+                                         np.zeros(n_tot, np.float32), np.zeros(n_tot, np.int32), starts,
+                                         np.array(lens, np.int32))
+    ref, _ = oracle.attend(small, np.concatenate(qs), scale)
+    assert attn_error(np.concatenate(out_rows), ref[0, 0]) <= ATTN_TOL
+
+    # ---- steady state: two more steps through the fused path, compared whole
+    del pre, src, meta, score_ref, keep_ref
+    cur, flip = spare[0], 1
+    hc = device_cache_to_host(w, cur)
+    for step in (1, 2):
+        inp = ki.decode_inputs(w, step, device=DEV)
+        now = now + 1
+        pos_new = np.full(w.nseg, now[0], np.int32)
+        kv.kvtrim_append(ctx, cur, inp["k_new"], inp["v_new"], inp["log_beta_new"], torch.from_numpy(pos_new).to(DEV), 1)
+        kv.kvtrim_score(ctx, cur, torch.from_numpy(now).to(DEV), score)
+        kv.kvtrim_select_global(ctx, cur, score, budget, keep, kept, thr)
+        nxt = spare[flip]
+        kv.kvtrim_compact_attn(ctx, cur, keep, kept, nxt, reserve, inp["q"], 0, w.n_layers, scale, out, lse)
+        assert kv.kvtrim_poll_error(ctx) == 0
+        oracle.append(hc, bf16_bits(inp["k_new"]), bf16_bits(inp["v_new"]), inp["log_beta_new"].cpu().numpy(), pos_new)
+        s_ref = oracle.score(hc, now)
+        k_ref, kept_r, thr_r = oracle.select(hc, s_ref, np.array([B], np.int64))
+        hc_next = oracle.compact(hc, k_ref, dst_cap, reserve)
+        out_ref, lse_ref = oracle.attend(hc_next, bf16_bits(inp["q"]), scale)
+        assert np.array_equal(kept.cpu().numpy(), kept_r) and thr.cpu().numpy().view(np.uint32)[0] == thr_r[0]
+        assert compare_caches(device_cache_to_host(w, nxt), hc_next)
+        assert attn_error(out.cpu().numpy(), out_ref) <= ATTN_TOL
+        assert np.abs(lse.cpu().numpy() - lse_ref).max() <= 2e-3
+        cur, flip, hc = nxt, flip ^ 1, hc_next
