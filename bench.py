@@ -29,14 +29,16 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def algorithmic_bytes(w, n_cand, n_ret):
+def algorithmic_bytes(w, n_cand, n_ret, horizon=1):
     """Bytes the method has to move per step (per-unit figures: 8 B/candidate for the score,
     5 B/candidate for the selection, 2*(4D+8) B per retained entry for the compaction,
-    4D B per retained entry + 6D B per query head for the attention)."""
+    4D B per retained entry + 6D B per query head for the attention; a lookahead horizon other
+    than 1 adds the 4-byte tail constant to the score's and the compaction's per-entry bytes)."""
     D = w.head_dim
-    R = 4 * D + 8
+    tail = 0 if horizon == 1 else 4
+    R = 4 * D + 8 + tail
     return {
-        "score": 8 * n_cand,
+        "score": (8 + tail) * n_cand,
         "select": 5 * n_cand,
         "compact": 2 * R * n_ret,
         "attend": 4 * D * n_ret + 6 * D * w.n_seq * w.n_layers * w.n_q_heads,
@@ -50,6 +52,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="long", choices=["long", "llama", "vlm", "tiny"])
     ap.add_argument("--prefill", type=int, default=None, help="override the prefilled length (scaled-down run)")
+    ap.add_argument("--horizon", type=int, default=1,
+                    help="lookahead horizon of the score: 1 = the metric's form, 2 = the paper's inference default, 0 = infinite")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size reference for rocprofv3 --pmc counters")
@@ -73,7 +77,7 @@ def main():
     n_steps = K + W + 1                       # + one extra step that is replayed on the CPU oracle
 
     t0 = time.time()
-    pre = ki.prefill_cache(w, reserve=reserve, device=dev)
+    pre = ki.with_horizon(ki.prefill_cache(w, reserve=reserve, device=dev), args.horizon)
     torch.cuda.synchronize()
     total0 = sum(w.prefill) * w.n_layers * w.n_kv_heads
     log(f"[bench] prefill cache: {total0} entries, {2 * total0 * w.head_dim * 2 / 1e9:.2f} GB K/V, "
@@ -83,7 +87,7 @@ def main():
     dst_cap = min(B, total0 + n_steps * w.nseg) + w.nseg * reserve + 8
     src = kv.Cache.from_dict(pre, dev)
     ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, max(src.cap, dst_cap))
-    spare = [kv.Cache.empty(w.nseg, w.head_dim, dst_cap, dev) for _ in range(2)]
+    spare = [kv.Cache.empty(w.nseg, w.head_dim, dst_cap, dev, with_tail=args.horizon != 1) for _ in range(2)]
     cap = max(src.cap, dst_cap)
     score = torch.zeros(cap, dtype=torch.float32, device=dev)
     keep = torch.zeros(cap, dtype=torch.uint8, device=dev)
@@ -99,7 +103,7 @@ def main():
     inputs, nows, pos_news = [], [], []
     now0 = np.array([t - 1 for t in w.prefill], np.int32)
     for s in range(n_steps):
-        inputs.append(ki.decode_inputs(w, s, device=dev))
+        inputs.append(ki.decode_inputs(w, s, device=dev, horizon=args.horizon))
         now = now0 + s + 1
         nows.append(torch.from_numpy(now).to(dev))
         pos_news.append(torch.from_numpy(np.repeat(now, per_seq).astype(np.int32)).to(dev))
@@ -110,7 +114,8 @@ def main():
     def step(s):
         inp = inputs[s]
         cur = state["src"]
-        kv.kvtrim_append(ctx, cur, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos_news[s], 1)
+        kv.kvtrim_append(ctx, cur, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos_news[s], 1,
+                         log_tail_new=inp.get("log_tail_new"))
         kv.kvtrim_score(ctx, cur, nows[s], score)
         kv.kvtrim_select_global(ctx, cur, score, budget, keep, kept, thr)
         dst = spare[state["flip"]]
@@ -159,7 +164,7 @@ def main():
     prof = kv.kvtrim_profile_end(ctx)
     assert kv.kvtrim_poll_error(ctx) == 0, "device-side error in the timed region"
     ms_per_step = (t_end - t_begin) * 1e3 / K
-    alg = algorithmic_bytes(w, n_cand, n_ret)
+    alg = algorithmic_bytes(w, n_cand, n_ret, args.horizon)
     alg_total = sum(alg.values())
     stage_model_bytes = None
     if args.unfused:
@@ -199,7 +204,8 @@ def main():
         "data": "synthetic",
         "config": {
             "workload": f"{w.name}: S{w.n_seq} L{w.n_layers} Hkv{w.n_kv_heads} Hq{w.n_q_heads} D{w.head_dim}, "
-                        f"{w.prefill[0]} prefilled, B={B} ({n_cand} candidates/step, {n_ret} retained)",
+                        f"{w.prefill[0]} prefilled, B={B} ({n_cand} candidates/step, {n_ret} retained), "
+                        f"score lookahead horizon {args.horizon if args.horizon > 0 else 'infinite'}",
             "stages": ("append, score, select_global, compact, decode_attn (five C-ABI calls per step)" if args.unfused else
                        "append, score, select_global, compact_attn (stages 3+4 fused; four C-ABI calls per step)"),
             "first_step_ms": first_ms,
@@ -227,7 +233,8 @@ def main():
         now = now0 + s + 1
         pos_new = np.repeat(now, per_seq).astype(np.int32)
         t_cpu = time.perf_counter()
-        oracle.append(hc, bf16_bits(inp["k_new"]), bf16_bits(inp["v_new"]), inp["log_beta_new"].numpy(), pos_new)
+        oracle.append(hc, bf16_bits(inp["k_new"]), bf16_bits(inp["v_new"]), inp["log_beta_new"].numpy(), pos_new,
+                      log_tail_new=inp["log_tail_new"].numpy() if args.horizon != 1 else None)
         score_ref = oracle.score(hc, now)
         keep_ref, kept_ref, thr_ref = oracle.select(hc, score_ref, np.array(list(w.budget), np.int64))
         hc_next = oracle.compact(hc, keep_ref, dst_cap, reserve)

@@ -34,6 +34,8 @@
  *      k, v       bf16 [cap_entries][head_dim], row-major, 16-byte aligned base
  *      log_beta   fp32 [cap_entries]   log of the retention coefficient, <= 0, not NaN
  *      pos        int32 [cap_entries]  token position of the entry
+ *      log_tail   fp32 [cap_entries] or NULL: only for a lookahead horizon H > 1 of the
+ *                 score, log(sum_{k<H} beta^k), fixed like beta when the token is cached
  *      seg_start  int64 [nseg]
  *      seg_len    int32 [nseg]
  *  Entries outside every segment are never read; what the calls leave in the
@@ -78,6 +80,7 @@ typedef struct {
     int64_t *seg_start;
     int32_t *seg_len;
     int64_t cap_entries;
+    float *log_tail; /* NULL = lookahead horizon 1 */
 } kvtrim_cache;
 
 /* Context life cycle (host side, synchronous).  kvtrim_create allocates the
@@ -91,10 +94,15 @@ const char *kvtrim_last_error(const kvtrim_ctx *ctx); /* host string, owned by c
  * sticky device flag (KVTRIM_OK, KVTRIM_ECAP, KVTRIM_EMISMATCH or KVTRIM_ELAYOUT). */
 kvtrim_status kvtrim_poll_error(kvtrim_ctx *ctx, void *hip_stream);
 
-/* Stage 1 - retention score, Sec. 4.2 Eq. (global_score) at lookahead T-t = 1,
- * in log domain:  score[e] = float(now[seq] + 1 - pos[e]) * log_beta[e], exactly
- * one IEEE binary32 multiply (round to nearest even).  now[seq] is the position of
- * the newest token of the sequence (device int32 [n_seq]).
+/* Stage 1 - retention score, Sec. 4.2 Eq. (global_score), in log domain.
+ * Lookahead T-t = 1 (c->log_tail == NULL):
+ *     score[e] = float(now[seq] + 1 - pos[e]) * log_beta[e],
+ * exactly one IEEE binary32 multiply (round to nearest even).
+ * Lookahead T-t = H > 1 or H -> infinity (c->log_tail != NULL; Sec. 5.1 uses H = 2):
+ *     score[e] = fma(float(now[seq] + 1 - pos[e]), log_beta[e], log_tail[e]),
+ * exactly one correctly rounded binary32 fused multiply-add; log_tail[e] is the
+ * log of the factor (1 - beta^H)/(1 - beta) of the equation.
+ * now[seq] is the position of the newest token of the sequence (device int32 [n_seq]).
  * score_out: device fp32 [cap_entries]; written for entries inside segments. */
 kvtrim_status kvtrim_score(kvtrim_ctx *ctx, const kvtrim_cache *c, const int32_t *now,
                            float *score_out, void *hip_stream);
@@ -116,7 +124,9 @@ kvtrim_status kvtrim_select_global(kvtrim_ctx *ctx, const kvtrim_cache *c, const
 /* Stage 3 - variable-length per-(layer, head) caches, Sec. 4.2 "Implementation
  * details", realised as a stable stream compaction: segment g of dst holds the
  * entries of src segment g with keep[e] != 0 in their original order (K row, V
- * row, log_beta, pos copied bit for bit), dst->seg_len[g] = kept[g] and
+ * row, log_beta, pos and - if both caches carry it - log_tail copied bit for bit;
+ * src->log_tail and dst->log_tail must both be NULL or both be set),
+ * dst->seg_len[g] = kept[g] and
  * dst->seg_start[g] = sum_{g' < g} (kept[g'] + reserve), i.e. `reserve` free slots
  * follow every segment.  src and dst must not share buffers.  keep: device uint8
  * [src->cap_entries]; kept: device int32 [nseg] as produced by stage 2.
@@ -152,13 +162,14 @@ kvtrim_status kvtrim_compact_attn(kvtrim_ctx *ctx, const kvtrim_cache *src, cons
 /* Support - new tokens enter the cache (Sec. 3.2: beta is fixed when the token is
  * first cached).  Appends n_new entries to every segment, in order, behind its
  * current end and adds n_new to seg_len.  k_new, v_new: device bf16
- * [nseg][n_new][head_dim]; log_beta_new: device fp32 [nseg][n_new]; pos_new: device
- * int32 [nseg][n_new] (ascending, above the segment's last position).
+ * [nseg][n_new][head_dim]; log_beta_new: device fp32 [nseg][n_new]; log_tail_new:
+ * device fp32 [nseg][n_new], required iff c->log_tail != NULL (NULL otherwise); pos_new:
+ * device int32 [nseg][n_new] (ascending, above the segment's last position).
  * Device-side error KVTRIM_ECAP if some segment lacks n_new free slots before the
  * next segment (or the end of the buffer); that segment is then left unchanged. */
 kvtrim_status kvtrim_append(kvtrim_ctx *ctx, kvtrim_cache *c, const void *k_new, const void *v_new,
-                            const float *log_beta_new, const int32_t *pos_new, int32_t n_new,
-                            void *hip_stream);
+                            const float *log_beta_new, const float *log_tail_new, const int32_t *pos_new,
+                            int32_t n_new, void *hip_stream);
 
 /* Instrumentation (for the benchmark; not a step of the method).  Between
  * kvtrim_profile_begin and kvtrim_profile_end every launch of a kernel whose bit is

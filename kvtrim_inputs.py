@@ -1,16 +1,18 @@
 """Seeded synthetic workloads for the kvtrim hot path.
 
 This module only draws random inputs (K/V rows, gate logits turned into
-log-retention values, queries, segment layouts).  It holds none of the
-method's arithmetic (no score, no selection, no compaction, no attention),
-so both the GPU path and the CPU oracle may be fed from it.
+the per-token constants a retention gate hands over when a token is cached,
+queries, segment layouts).  It holds none of the hot path's arithmetic (no
+score, no selection, no compaction, no attention), so both the GPU path and
+the CPU oracle may be fed from it.
 
 The five named workloads have the shapes, value distributions and structure
 of the benchmark configurations; every one can be scaled down (shorter
 prefill, proportionally smaller budget) for tests.  "N(m, s)" always means
 mean m and standard deviation s.  A retention gate emits beta = sigmoid(z)
 (Sec. 4.1); the cache stores log(beta) = -log1p(exp(-z)), evaluated in fp64
-and rounded once to fp32.
+and rounded once to fp32, and - only when the score's lookahead horizon H is
+not 1 - log(sum_{k<H} beta^k), likewise fp64 rounded once to fp32.
 """
 from dataclasses import dataclass, replace
 from typing import Tuple
@@ -97,6 +99,22 @@ def _log_beta_of_z(z64: torch.Tensor) -> torch.Tensor:
     return (-torch.log1p(torch.exp(-z64))).to(torch.float32)
 
 
+def log_tail_of(log_beta: torch.Tensor, horizon: int) -> torch.Tensor:
+    """The per-token constant that comes with log(beta) when the lookahead horizon of the score is
+    H = `horizon` > 1 (0 means the limit H -> infinity): log(sum_{k<H} beta^k), evaluated in fp64 and
+    rounded once to fp32 (Sec. 4.2, Eq. global_score: the factor (1 - beta^H) / (1 - beta))."""
+    lb = log_beta.to(torch.float64)
+    beta = torch.exp(lb)
+    if horizon <= 0:
+        return (-torch.log1p(-beta)).to(torch.float32)
+    total = torch.zeros_like(beta)
+    term = torch.ones_like(beta)
+    for _ in range(int(horizon)):
+        total += term
+        term = term * beta
+    return torch.log(total).to(torch.float32)
+
+
 def prefill_log_beta(w: Workload, seq: int, device="cpu") -> torch.Tensor:
     """log(beta) of the prefilled tokens of one sequence, fp32 [L*Hkv, T]."""
     T = w.prefill[seq]
@@ -127,8 +145,9 @@ def rows(w: Workload, n: int, device, *salt) -> torch.Tensor:
     return torch.randn(n, w.head_dim, generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
 
 
-def decode_inputs(w: Workload, step: int, device="cpu"):
-    """Inputs of decode step `step` (0-based): one new token per segment and one query per head."""
+def decode_inputs(w: Workload, step: int, device="cpu", horizon: int = 1):
+    """Inputs of decode step `step` (0-based): one new token per segment and one query per head
+    (plus the horizon tail constant of the new tokens when horizon != 1)."""
     g = _gen(w, device, 6, step)
     nseg, D = w.nseg, w.head_dim
     k_new = torch.randn(nseg, D, generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
@@ -136,7 +155,10 @@ def decode_inputs(w: Workload, step: int, device="cpu"):
     z = torch.randn(nseg, generator=g, device=device, dtype=torch.float64) * w.z_std + w.z_mean
     q = torch.randn(w.n_seq, w.n_layers, w.n_q_heads, D, generator=g, device=device,
                     dtype=torch.float32).to(torch.bfloat16)
-    return {"k_new": k_new, "v_new": v_new, "log_beta_new": _log_beta_of_z(z), "q": q}
+    d = {"k_new": k_new, "v_new": v_new, "log_beta_new": _log_beta_of_z(z), "q": q}
+    if horizon != 1:
+        d["log_tail_new"] = log_tail_of(d["log_beta_new"], horizon)
+    return d
 
 
 def alloc_cache(w: Workload, cap: int, device="cpu"):
@@ -151,6 +173,14 @@ def alloc_cache(w: Workload, cap: int, device="cpu"):
         "seg_len": torch.zeros(w.nseg, dtype=torch.int32, device=device),
         "cap": cap,
     }
+
+
+def with_horizon(cache: dict, horizon: int) -> dict:
+    """Adds the per-entry horizon tail constant to a cache made by prefill_cache / ragged_cache."""
+    if horizon != 1:
+        cache = dict(cache)
+        cache["log_tail"] = log_tail_of(cache["log_beta"], horizon)
+    return cache
 
 
 def prefill_cache(w: Workload, reserve: int = 1, device="cpu"):

@@ -31,7 +31,7 @@ class _CShape(C.Structure):
 
 class _CCache(C.Structure):
     _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("log_beta", C.c_void_p), ("pos", C.c_void_p),
-                ("seg_start", C.c_void_p), ("seg_len", C.c_void_p), ("cap", C.c_int64)]
+                ("seg_start", C.c_void_p), ("seg_len", C.c_void_p), ("cap", C.c_int64), ("log_tail", C.c_void_p)]
 
 
 def lib():
@@ -70,9 +70,10 @@ class Shape:
 class HostCache:
     """Ragged cache in host memory.  k, v hold bf16 bit patterns as uint16."""
 
-    def __init__(self, shape, cap, with_rows=True):
+    def __init__(self, shape, cap, with_rows=True, with_tail=False):
         self.shape = shape
         self.cap = int(cap)
+        self.log_tail = np.zeros(self.cap, np.float32) if with_tail else None
         D = shape.head_dim
         rows = self.cap if with_rows else 0          # metadata-only caches serve score / select
         self.k = np.zeros((rows, D), np.uint16)
@@ -83,8 +84,9 @@ class HostCache:
         self.seg_len = np.zeros(shape.nseg, np.int32)
 
     @classmethod
-    def from_arrays(cls, shape, k, v, log_beta, pos, seg_start, seg_len):
+    def from_arrays(cls, shape, k, v, log_beta, pos, seg_start, seg_len, log_tail=None):
         self = cls.__new__(cls)
+        self.log_tail = None if log_tail is None else np.ascontiguousarray(log_tail, np.float32)
         self.shape = shape
         self.cap = int(log_beta.shape[0])
         self.k = np.ascontiguousarray(k, np.uint16).reshape(-1, shape.head_dim)
@@ -98,7 +100,7 @@ class HostCache:
     def c(self):
         p = lambda a: a.ctypes.data_as(C.c_void_p)
         return _CCache(p(self.k), p(self.v), p(self.log_beta), p(self.pos), p(self.seg_start),
-                       p(self.seg_len), self.cap)
+                       p(self.seg_len), self.cap, None if self.log_tail is None else p(self.log_tail))
 
     def entry_index(self):
         """Flat indices of every live entry, in (segment, position) order."""
@@ -150,7 +152,7 @@ def select(cache, score_arr, budget):
 
 def compact(src, keep, dst_cap, reserve):
     keep = np.ascontiguousarray(keep, np.uint8)
-    dst = HostCache(src.shape, dst_cap)
+    dst = HostCache(src.shape, dst_cap, with_tail=src.log_tail is not None)
     sh, cs, cd = src.shape.c(), src.c(), dst.c()
     rc = lib().kvo_compact(C.byref(sh), C.byref(cs), _p(keep), C.byref(cd), C.c_int32(int(reserve)))
     if rc != 0:
@@ -171,15 +173,20 @@ def attend(cache, q, scale, layer_begin=0, layer_end=None, want_lse=True):
     return out, lse
 
 
-def append(cache, k_new, v_new, log_beta_new, pos_new):
+def append(cache, k_new, v_new, log_beta_new, pos_new, log_tail_new=None):
     sh = cache.shape
     log_beta_new = np.ascontiguousarray(log_beta_new, np.float32).reshape(sh.nseg, -1)
     n_new = log_beta_new.shape[1]
     k_new = np.ascontiguousarray(k_new, np.uint16).reshape(sh.nseg, n_new, sh.head_dim)
     v_new = np.ascontiguousarray(v_new, np.uint16).reshape(sh.nseg, n_new, sh.head_dim)
     pos_new = np.ascontiguousarray(pos_new, np.int32).reshape(sh.nseg, n_new)
+    if cache.log_tail is not None:
+        assert log_tail_new is not None, "this cache carries a horizon tail: log_tail_new is required"
+        log_tail_new = np.ascontiguousarray(log_tail_new, np.float32).reshape(sh.nseg, n_new)
+    else:
+        log_tail_new = None
     csh, cc = sh.c(), cache.c()
-    rc = lib().kvo_append(C.byref(csh), C.byref(cc), _p(k_new), _p(v_new), _p(log_beta_new), _p(pos_new),
-                          C.c_int32(n_new))
+    rc = lib().kvo_append(C.byref(csh), C.byref(cc), _p(k_new), _p(v_new), _p(log_beta_new),
+                          None if log_tail_new is None else _p(log_tail_new), _p(pos_new), C.c_int32(n_new))
     if rc != 0:
         raise OverflowError("oracle append: no room in a segment")

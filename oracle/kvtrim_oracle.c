@@ -6,8 +6,12 @@
  * with the HIP path, and the product path never calls it.
  *
  * What it defines (all citations are to the paper):
- *   kvo_score    Sec. 4.2, Eq. (global_score) at lookahead horizon T-t = 1, in
- *                log domain: log G~ = (t+1-i) * log(beta).          [pinned]
+ *   kvo_score    Sec. 4.2, Eq. (global_score) in log domain.  At lookahead horizon
+ *                T-t = 1: log G~ = (t+1-i) * log(beta), one fp32 multiply.  For a
+ *                longer horizon H the cache carries, per entry, the constant
+ *                log_tail = log(sum_{k<H} beta^k) fixed when the token was cached,
+ *                and log G~ = fma(t+1-i, log(beta), log_tail), one fp32 fused
+ *                multiply-add.                                       [pinned]
  *   kvo_score_horizon
  *                Sec. 4.2, Eq. (global_score) for a general horizon H = T-t,
  *                log domain, fp64.                                   [pinned]
@@ -36,6 +40,7 @@
  * are HOST pointers):
  *   k, v       bf16 bit patterns, [cap][D] row-major
  *   log_beta   fp32 [cap]
+ *   log_tail   fp32 [cap] or NULL (NULL = horizon 1): log of the geometric tail sum
  *   pos        int32 [cap], strictly ascending inside a segment
  *   seg_start  int64 [nseg], nseg = S*L*Hkv, segment g = (seq*L + layer)*Hkv + head
  *   seg_len    int32 [nseg]
@@ -56,6 +61,7 @@ typedef struct {
     int64_t *seg_start;
     int32_t *seg_len;
     int64_t cap;
+    float *log_tail;
 } kvo_cache;
 
 static int64_t kvo_nseg(const kvo_shape *sh) {
@@ -79,9 +85,11 @@ static uint32_t kvo_key32(float s) {
 
 uint32_t kvo_key_of_score(float s) { return kvo_key32(s); }
 
-/* Sec. 4.2, Eq. (global_score), T-t = 1: G~ = beta^(t+1-i); in log domain this
+/* Sec. 4.2, Eq. (global_score).  T-t = 1: G~ = beta^(t+1-i); in log domain this
  * is one binary32 multiply of the (exactly representable) elapsed-step count
- * with log(beta). */
+ * with log(beta).  With a horizon tail: G~ = beta^(t+1-i) * sum_{k<H} beta^k, in
+ * log domain one correctly rounded binary32 fused multiply-add with the cached
+ * log of the tail sum. */
 void kvo_score(const kvo_shape *sh, const kvo_cache *c, const int32_t *now, float *score_out) {
     int64_t nseg = kvo_nseg(sh);
     int64_t per_seq = (int64_t)sh->n_layers * sh->n_kv_heads;
@@ -91,8 +99,12 @@ void kvo_score(const kvo_shape *sh, const kvo_cache *c, const int32_t *now, floa
             int64_t e = c->seg_start[g] + j;
             int32_t elapsed = now[seq] + 1 - c->pos[e];
             volatile float fe = (float)elapsed; /* volatile: no contraction, no widening */
-            volatile float s = fe * c->log_beta[e];
-            score_out[e] = s;
+            if (c->log_tail) {
+                score_out[e] = fmaf(fe, c->log_beta[e], c->log_tail[e]);
+            } else {
+                volatile float s = fe * c->log_beta[e];
+                score_out[e] = s;
+            }
         }
     }
 }
@@ -211,6 +223,7 @@ int kvo_compact(const kvo_shape *sh, const kvo_cache *src, const uint8_t *keep, 
             memcpy(dst->k + d * D, src->k + e * D, (size_t)D * 2);
             memcpy(dst->v + d * D, src->v + e * D, (size_t)D * 2);
             dst->log_beta[d] = src->log_beta[e];
+            if (src->log_tail && dst->log_tail) dst->log_tail[d] = src->log_tail[e];
             dst->pos[d] = src->pos[e];
             ++out;
         }
@@ -270,10 +283,11 @@ void kvo_attend(const kvo_shape *sh, const kvo_cache *c, const uint16_t *q, int3
 
 /* A new token (or n_new consecutive tokens) enters every segment: rows are
  * written behind the segment's current end.  k_new/v_new are [nseg][n_new][D],
- * log_beta_new/pos_new are [nseg][n_new].  Returns 0, or -4 when a segment has
+ * log_beta_new/log_tail_new/pos_new are [nseg][n_new] (log_tail_new only for caches
+ * that carry a horizon tail).  Returns 0, or -4 when a segment has
  * no room before the next segment's start (or the end of the buffer). */
 int kvo_append(const kvo_shape *sh, kvo_cache *c, const uint16_t *k_new, const uint16_t *v_new,
-               const float *log_beta_new, const int32_t *pos_new, int32_t n_new) {
+               const float *log_beta_new, const float *log_tail_new, const int32_t *pos_new, int32_t n_new) {
     int64_t nseg = kvo_nseg(sh);
     int D = sh->head_dim;
     for (int64_t g = 0; g < nseg; ++g) {
@@ -287,6 +301,7 @@ int kvo_append(const kvo_shape *sh, kvo_cache *c, const uint16_t *k_new, const u
             memcpy(c->k + e * D, k_new + (g * n_new + r) * D, (size_t)D * 2);
             memcpy(c->v + e * D, v_new + (g * n_new + r) * D, (size_t)D * 2);
             c->log_beta[e] = log_beta_new[g * n_new + r];
+            if (c->log_tail && log_tail_new) c->log_tail[e] = log_tail_new[g * n_new + r];
             c->pos[e] = pos_new[g * n_new + r];
         }
         c->seg_len[g] += n_new;

@@ -31,7 +31,8 @@ class _Config(C.Structure):
 
 class _Cache(C.Structure):
     _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("log_beta", C.c_void_p), ("pos", C.c_void_p),
-                ("seg_start", C.c_void_p), ("seg_len", C.c_void_p), ("cap_entries", C.c_int64)]
+                ("seg_start", C.c_void_p), ("seg_len", C.c_void_p), ("cap_entries", C.c_int64),
+                ("log_tail", C.c_void_p)]
 
 
 def library_path():
@@ -63,7 +64,7 @@ def load_library():
                                             C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p,
                                             C.c_void_p, C.c_void_p]
         lib.kvtrim_append.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.c_void_p,
-                                      C.c_void_p, C.c_int32, C.c_void_p]
+                                      C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
         lib.kvtrim_profile_begin.argtypes = [C.c_void_p, C.c_uint32]
         lib.kvtrim_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         lib.kvtrim_kernel_name.argtypes = [C.c_int32]
@@ -102,26 +103,31 @@ def _stream(stream):
 class Cache:
     """Ragged cache: device tensors plus the C view of them."""
 
-    def __init__(self, k, v, log_beta, pos, seg_start, seg_len):
+    def __init__(self, k, v, log_beta, pos, seg_start, seg_len, log_tail=None):
         self.k, self.v, self.log_beta, self.pos, self.seg_start, self.seg_len = k, v, log_beta, pos, seg_start, seg_len
+        self.log_tail = log_tail
         self.cap = int(log_beta.shape[0])
         self.c = _Cache(_ptr(k, torch.bfloat16).value, _ptr(v, torch.bfloat16).value,
                         _ptr(log_beta, torch.float32).value, _ptr(pos, torch.int32).value,
-                        _ptr(seg_start, torch.int64).value, _ptr(seg_len, torch.int32).value, self.cap)
+                        _ptr(seg_start, torch.int64).value, _ptr(seg_len, torch.int32).value, self.cap,
+                        None if log_tail is None else _ptr(log_tail, torch.float32).value)
 
     @classmethod
     def from_dict(cls, d, device="cuda"):
         t = {n: d[n].to(device) for n in ("k", "v", "log_beta", "pos", "seg_start", "seg_len")}
+        if d.get("log_tail") is not None:
+            t["log_tail"] = d["log_tail"].to(device)
         return cls(**t)
 
     @classmethod
-    def empty(cls, nseg, head_dim, cap, device="cuda"):
+    def empty(cls, nseg, head_dim, cap, device="cuda", with_tail=False):
         return cls(torch.zeros(cap, head_dim, dtype=torch.bfloat16, device=device),
                    torch.zeros(cap, head_dim, dtype=torch.bfloat16, device=device),
                    torch.zeros(cap, dtype=torch.float32, device=device),
                    torch.zeros(cap, dtype=torch.int32, device=device),
                    torch.zeros(nseg, dtype=torch.int64, device=device),
-                   torch.zeros(nseg, dtype=torch.int32, device=device))
+                   torch.zeros(nseg, dtype=torch.int32, device=device),
+                   torch.zeros(cap, dtype=torch.float32, device=device) if with_tail else None)
 
 
 class Context:
@@ -200,10 +206,11 @@ def kvtrim_compact_attn(ctx, src, keep, kept, dst, reserve, q, layer_begin, laye
         _ptr(lse, torch.float32), _stream(stream)), "kvtrim_compact_attn")
 
 
-def kvtrim_append(ctx, cache, k_new, v_new, log_beta_new, pos_new, n_new, stream=None):
+def kvtrim_append(ctx, cache, k_new, v_new, log_beta_new, pos_new, n_new, log_tail_new=None, stream=None):
     _check(ctx, load_library().kvtrim_append(ctx.handle, C.byref(cache.c), _ptr(k_new, torch.bfloat16),
                                              _ptr(v_new, torch.bfloat16), _ptr(log_beta_new, torch.float32),
-                                             _ptr(pos_new, torch.int32), int(n_new), _stream(stream)),
+                                             _ptr(log_tail_new, torch.float32), _ptr(pos_new, torch.int32),
+                                             int(n_new), _stream(stream)),
            "kvtrim_append")
 
 

@@ -161,6 +161,7 @@ __global__ __launch_bounds__(CMP_THREADS) void k_cmp_copy(CacheView src, const u
     if (flag) {
         list[rank] = tid;
         dst.log_beta[dbase + rank] = src.log_beta[sbase + tid];
+        if (src.log_tail) dst.log_tail[dbase + rank] = src.log_tail[sbase + tid];
         dst.pos[dbase + rank] = src.pos[sbase + tid];
     }
     __syncthreads();

@@ -115,6 +115,7 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
     if (flag) {
         list[rank] = tid;
         dst.log_beta[dbase + rank] = src.log_beta[sbase + tid];
+        if (src.log_tail) dst.log_tail[dbase + rank] = src.log_tail[sbase + tid];
         dst.pos[dbase + rank] = src.pos[sbase + tid];
     }
     __syncthreads();
@@ -301,7 +302,7 @@ kvtrim_status launch_compact_attn(kvtrim_ctx* ctx, const CacheView& src, const u
         if (rc != KVTRIM_OK) return rc;
         CacheView d;
         d.k = dst.k; d.v = dst.v; d.log_beta = dst.log_beta; d.pos = dst.pos;
-        d.seg_start = dst.seg_start; d.seg_len = dst.seg_len; d.cap = dst.cap;
+        d.seg_start = dst.seg_start; d.seg_len = dst.seg_len; d.cap = dst.cap; d.log_tail = dst.log_tail;
         return launch_attn(ctx, d, q, layer_begin, layer_end, scale, out, lse, st);
     }
     launch_cmp_scan(ctx, src, keep, kept, dst, reserve, st);

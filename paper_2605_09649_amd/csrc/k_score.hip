@@ -3,8 +3,10 @@
 
 namespace kvtrim {
 
-// Sec. 4.2, Eq. (global_score) at lookahead 1: log G~ = (now + 1 - pos) * log(beta), one fp32
-// multiply.  `bps` blocks share a segment and stride over its entries.
+// Sec. 4.2, Eq. (global_score) in log domain.  Lookahead 1: log G~ = (now + 1 - pos) * log(beta),
+// one fp32 multiply.  Longer lookahead: the cached log of the tail sum is added by the same
+// instruction, one correctly rounded fp32 fused multiply-add.  `bps` blocks share a segment and
+// stride over its entries.
 __global__ __launch_bounds__(256) void k_score(CacheView c, const int32_t* __restrict__ now,
                                                float* __restrict__ score, int segs_per_seq, int bps) {
     const int seg = blockIdx.x / bps, part = blockIdx.x % bps;
@@ -15,8 +17,14 @@ __global__ __launch_bounds__(256) void k_score(CacheView c, const int32_t* __res
     const float* lb = c.log_beta + start;
     const int32_t* pos = c.pos + start;
     float* out = score + start;
-    for (int j = part * 256 + threadIdx.x; j < len; j += bps * 256)
-        out[j] = __fmul_rn((float)(t1 - pos[j]), lb[j]);
+    if (c.log_tail) {
+        const float* lt = c.log_tail + start;
+        for (int j = part * 256 + threadIdx.x; j < len; j += bps * 256)
+            out[j] = __fmaf_rn((float)(t1 - pos[j]), lb[j], lt[j]);
+    } else {
+        for (int j = part * 256 + threadIdx.x; j < len; j += bps * 256)
+            out[j] = __fmul_rn((float)(t1 - pos[j]), lb[j]);
+    }
 }
 
 kvtrim_status launch_score(kvtrim_ctx* ctx, const CacheView& c, const int32_t* now, float* score,
@@ -36,6 +44,7 @@ kvtrim_status launch_score(kvtrim_ctx* ctx, const CacheView& c, const int32_t* n
 __global__ __launch_bounds__(256) void k_append(CacheViewMut c, const uint16_t* __restrict__ k_new,
                                                 const uint16_t* __restrict__ v_new,
                                                 const float* __restrict__ lb_new,
+                                                const float* __restrict__ lt_new,
                                                 const int32_t* __restrict__ pos_new, int n_new, int nseg,
                                                 int head_dim, int32_t* err) {
     const int seg = blockIdx.x;
@@ -57,6 +66,7 @@ __global__ __launch_bounds__(256) void k_append(CacheViewMut c, const uint16_t* 
     }
     for (int i = threadIdx.x; i < n_new; i += blockDim.x) {
         c.log_beta[start + len + i] = lb_new[(int64_t)seg * n_new + i];
+        if (c.log_tail) c.log_tail[start + len + i] = lt_new[(int64_t)seg * n_new + i];
         c.pos[start + len + i] = pos_new[(int64_t)seg * n_new + i];
     }
     __syncthreads();
@@ -64,10 +74,11 @@ __global__ __launch_bounds__(256) void k_append(CacheViewMut c, const uint16_t* 
 }
 
 kvtrim_status launch_append(kvtrim_ctx* ctx, const CacheViewMut& c, const uint16_t* k_new, const uint16_t* v_new,
-                            const float* lb_new, const int32_t* pos_new, int32_t n_new, hipStream_t st) {
+                            const float* lb_new, const float* lt_new, const int32_t* pos_new, int32_t n_new,
+                            hipStream_t st) {
     const Shape& sh = ctx->shape;
     ProfScope prof(ctx, K_APPEND, st);
-    hipLaunchKernelGGL(k_append, dim3(sh.nseg), dim3(256), 0, st, c, k_new, v_new, lb_new, pos_new, n_new,
+    hipLaunchKernelGGL(k_append, dim3(sh.nseg), dim3(256), 0, st, c, k_new, v_new, lb_new, lt_new, pos_new, n_new,
                        sh.nseg, sh.head_dim, ctx->ws.err);
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;

@@ -87,6 +87,7 @@ static CacheView view_of(const kvtrim_cache* c) {
     v.seg_start = c->seg_start;
     v.seg_len = c->seg_len;
     v.cap = c->cap_entries;
+    v.log_tail = c->log_tail;
     return v;
 }
 
@@ -99,6 +100,7 @@ static CacheViewMut view_mut_of(const kvtrim_cache* c) {
     v.seg_start = c->seg_start;
     v.seg_len = c->seg_len;
     v.cap = c->cap_entries;
+    v.log_tail = c->log_tail;
     return v;
 }
 
@@ -299,6 +301,8 @@ kvtrim_status kvtrim_compact(kvtrim_ctx* ctx, const kvtrim_cache* src, const uin
     if (src->k == dst->k || src->v == dst->v || src->log_beta == dst->log_beta || src->pos == dst->pos ||
         src->seg_start == dst->seg_start || src->seg_len == dst->seg_len)
         return invalid(ctx, "src and dst share a buffer");
+    if ((src->log_tail == nullptr) != (dst->log_tail == nullptr) || (src->log_tail && src->log_tail == dst->log_tail))
+        return invalid(ctx, "log_tail must be set in both caches or in neither, and not shared");
     return launch_compact(ctx, view_of(src), keep, kept, view_mut_of(dst), reserve, (hipStream_t)hip_stream);
 }
 
@@ -327,6 +331,8 @@ kvtrim_status kvtrim_compact_attn(kvtrim_ctx* ctx, const kvtrim_cache* src, cons
     if (src->k == dst->k || src->v == dst->v || src->log_beta == dst->log_beta || src->pos == dst->pos ||
         src->seg_start == dst->seg_start || src->seg_len == dst->seg_len)
         return invalid(ctx, "src and dst share a buffer");
+    if ((src->log_tail == nullptr) != (dst->log_tail == nullptr) || (src->log_tail && src->log_tail == dst->log_tail))
+        return invalid(ctx, "log_tail must be set in both caches or in neither, and not shared");
     if (!q || !out) return invalid(ctx, "q / out is NULL");
     if (((uintptr_t)q) & 15) return invalid(ctx, "q not 16-byte aligned");
     if (layer_begin < 0 || layer_end > ctx->cfg.n_layers || layer_begin >= layer_end)
@@ -337,14 +343,17 @@ kvtrim_status kvtrim_compact_attn(kvtrim_ctx* ctx, const kvtrim_cache* src, cons
 }
 
 kvtrim_status kvtrim_append(kvtrim_ctx* ctx, kvtrim_cache* c, const void* k_new, const void* v_new,
-                            const float* log_beta_new, const int32_t* pos_new, int32_t n_new, void* hip_stream) {
+                            const float* log_beta_new, const float* log_tail_new, const int32_t* pos_new,
+                            int32_t n_new, void* hip_stream) {
     if (!ctx) return KVTRIM_EINVAL;
     if (const char* p = cache_problem(ctx, c, true)) return invalid(ctx, p);
     if (!k_new || !v_new || !log_beta_new || !pos_new) return invalid(ctx, "a new-token pointer is NULL");
     if ((((uintptr_t)k_new) | ((uintptr_t)v_new)) & 15) return invalid(ctx, "k_new / v_new not 16-byte aligned");
     if (n_new < 1) return invalid(ctx, "n_new < 1");
+    if ((c->log_tail == nullptr) != (log_tail_new == nullptr))
+        return invalid(ctx, "log_tail_new is required exactly when the cache carries log_tail");
     return launch_append(ctx, view_mut_of(c), (const uint16_t*)k_new, (const uint16_t*)v_new, log_beta_new,
-                         pos_new, n_new, (hipStream_t)hip_stream);
+                         log_tail_new, pos_new, n_new, (hipStream_t)hip_stream);
 }
 
 }  // extern "C"

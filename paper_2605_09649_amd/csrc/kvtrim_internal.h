@@ -37,6 +37,7 @@ struct CacheView {                   // device pointers, passed by value to kern
     const int64_t* seg_start;
     const int32_t* seg_len;
     int64_t cap;
+    const float* log_tail;           // NULL = lookahead horizon 1
 };
 
 struct CacheViewMut {
@@ -47,6 +48,7 @@ struct CacheViewMut {
     int64_t* seg_start;
     int32_t* seg_len;
     int64_t cap;
+    float* log_tail;
 };
 
 // Per-sequence state of the radix select, kept in the workspace.
@@ -139,7 +141,8 @@ kvtrim_status launch_compact_attn(kvtrim_ctx*, const CacheView& src, const uint8
                                   int32_t layer_begin, int32_t layer_end, float scale, float* out, float* lse,
                                   hipStream_t);
 kvtrim_status launch_append(kvtrim_ctx*, const CacheViewMut&, const uint16_t* k_new, const uint16_t* v_new,
-                            const float* lb_new, const int32_t* pos_new, int32_t n_new, hipStream_t);
+                            const float* lb_new, const float* lt_new, const int32_t* pos_new, int32_t n_new,
+                            hipStream_t);
 
 kvtrim_status hip_fail(kvtrim_ctx* ctx, hipError_t e, const char* what);
 

@@ -12,7 +12,7 @@ from helpers import bf16_bits, host_cache, live_mask
 
 
 def device_cache_to_host(w, dc):
-    d = {n: getattr(dc, n) for n in ("k", "v", "log_beta", "pos", "seg_start", "seg_len")}
+    d = {n: getattr(dc, n) for n in ("k", "v", "log_beta", "pos", "seg_start", "seg_len", "log_tail")}
     return host_cache(w, d)
 
 
@@ -25,6 +25,11 @@ def compare_caches(hc_gpu, hc_ref):
     if m[n:].any():
         return False
     m = m[:n]
+    if (hc_gpu.log_tail is None) != (hc_ref.log_tail is None):
+        return False
+    if hc_ref.log_tail is not None and not np.array_equal(hc_gpu.log_tail[:n][m].view(np.uint32),
+                                                          hc_ref.log_tail[:n][m].view(np.uint32)):
+        return False
     return (np.array_equal(hc_gpu.k[:n][m], hc_ref.k[:n][m]) and np.array_equal(hc_gpu.v[:n][m], hc_ref.v[:n][m])
             and np.array_equal(hc_gpu.log_beta[:n][m].view(np.uint32), hc_ref.log_beta[:n][m].view(np.uint32))
             and np.array_equal(hc_gpu.pos[:n][m], hc_ref.pos[:n][m]))
@@ -46,7 +51,8 @@ class GpuLoop:
         dst_cap = min(int(sum(budget)), total + extra_entries) + w.nseg * reserve + 8
         self.ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim,
                               max(self.src.cap, dst_cap))
-        self.spare = [kv.Cache.empty(w.nseg, w.head_dim, dst_cap, device) for _ in range(2)]
+        self.spare = [kv.Cache.empty(w.nseg, w.head_dim, dst_cap, device, with_tail=self.src.log_tail is not None)
+                      for _ in range(2)]
         cap = max(self.src.cap, dst_cap)
         self.score = torch.zeros(cap, dtype=torch.float32, device=device)
         self.keep = torch.zeros(cap, dtype=torch.uint8, device=device)
@@ -60,7 +66,8 @@ class GpuLoop:
 
     def step(self, inp, now_dev, pos_new_dev):
         ctx = self.ctx
-        kv.kvtrim_append(ctx, self.src, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos_new_dev, 1)
+        kv.kvtrim_append(ctx, self.src, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos_new_dev, 1,
+                         log_tail_new=inp.get("log_tail_new"))
         kv.kvtrim_score(ctx, self.src, now_dev, self.score)
         kv.kvtrim_select_global(ctx, self.src, self.score, self.budget, self.keep, self.kept, self.thr)
         dst = self.spare[self.flip]
@@ -79,11 +86,12 @@ class GpuLoop:
         self.flip ^= 1
 
 
-def run_steps_both(w, steps, budget, device="cuda:0", reserve=1, cache_dict=None, now0=None, fused=False):
+def run_steps_both(w, steps, budget, device="cuda:0", reserve=1, cache_dict=None, now0=None, fused=False, horizon=1):
     """Returns one dict per step with the comparison results."""
     if cache_dict is None:
         cache_dict = ki.prefill_cache(w, reserve=reserve)
         now0 = [t - 1 for t in w.prefill]
+    cache_dict = ki.with_horizon(cache_dict, horizon)
     hc = host_cache(w, cache_dict)
     gpu = GpuLoop(w, cache_dict, budget, reserve, steps * w.nseg, device, fused=fused)
     budget_np = np.array(list(budget), np.int64)
@@ -91,11 +99,12 @@ def run_steps_both(w, steps, budget, device="cuda:0", reserve=1, cache_dict=None
     per_seq = w.n_layers * w.n_kv_heads
     results = []
     for step in range(steps):
-        inp = ki.decode_inputs(w, step)
+        inp = ki.decode_inputs(w, step, horizon=horizon)
         now = now + 1
         pos_new = np.repeat(now, per_seq).astype(np.int32)
         # ---- oracle
-        oracle.append(hc, bf16_bits(inp["k_new"]), bf16_bits(inp["v_new"]), inp["log_beta_new"].numpy(), pos_new)
+        oracle.append(hc, bf16_bits(inp["k_new"]), bf16_bits(inp["v_new"]), inp["log_beta_new"].numpy(), pos_new,
+                      log_tail_new=None if horizon == 1 else inp["log_tail_new"].numpy())
         score_ref = oracle.score(hc, now)
         keep_ref, kept_ref, thr_ref = oracle.select(hc, score_ref, budget_np)
         dst_cap = gpu.spare[0].cap

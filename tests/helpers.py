@@ -23,7 +23,8 @@ def host_cache(w, c):
     return oracle.HostCache.from_arrays(
         shape_of(w), bf16_bits(c["k"]).copy(), bf16_bits(c["v"]).copy(),
         c["log_beta"].cpu().numpy().copy(), c["pos"].cpu().numpy().copy(),
-        c["seg_start"].cpu().numpy().copy(), c["seg_len"].cpu().numpy().copy())
+        c["seg_start"].cpu().numpy().copy(), c["seg_len"].cpu().numpy().copy(),
+        log_tail=None if c.get("log_tail") is None else c["log_tail"].cpu().numpy().copy())
 
 
 def live_mask(hc):

@@ -73,6 +73,32 @@ def test_one_giant_segment_and_many_empty_ones(fused):
     check(run_steps_both(w, steps=2, budget=[20011], device=DEV, cache_dict=c, now0=now.numpy(), fused=fused))
 
 
+@pytest.mark.parametrize("fused", [False, True])
+@pytest.mark.parametrize("horizon", [2, 5, 0])
+def test_lookahead_horizon_scores_through_the_whole_loop(horizon, fused):
+    # Sec. 4.2: horizon T-t = 2 is the paper's inference default, 0 stands for the limit T-t -> infinity
+    w = ki.workload("tiny", prefill=700)
+    check(run_steps_both(w, steps=6, budget=w.budget, device=DEV, fused=fused, horizon=horizon))
+    w = ki.workload("llama", prefill=600)
+    check(run_steps_both(w, steps=2, budget=w.budget, device=DEV, fused=fused, horizon=horizon))
+
+
+def test_horizon_tail_must_be_consistent_between_caches():
+    w = wl(1, 1, 2, 2, 64)
+    c, now = ki.ragged_cache(w, [10, 10], salt=1)
+    ctx = kv.Context(1, 1, 2, 4, 64, 32)
+    src = kv.Cache.from_dict(ki.with_horizon(c, 2), DEV)
+    dst = kv.Cache.empty(2, 64, 32, DEV)                                  # no tail in the destination
+    keep = torch.ones(32, dtype=torch.uint8, device=DEV)
+    kept = torch.tensor([10, 10], dtype=torch.int32, device=DEV)
+    with pytest.raises(kv.KvtrimError):
+        kv.kvtrim_compact(ctx, src, keep, kept, dst, 1)
+    new = ki.decode_inputs(w, 0)
+    with pytest.raises(kv.KvtrimError):                                   # tail required for this cache
+        kv.kvtrim_append(ctx, src, new["k_new"].to(DEV), new["v_new"].to(DEV), new["log_beta_new"].to(DEV),
+                         torch.zeros(2, dtype=torch.int32, device=DEV), 1)
+
+
 def test_fused_call_with_a_layer_range_and_sparse_mask():
     # fused compaction + attention on a mask that keeps about one entry in five, layers [1, 3) only
     w = wl(2, 3, 2, 4, 128)

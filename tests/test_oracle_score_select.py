@@ -8,6 +8,7 @@ force of the eviction rule, and closed forms / invariants of the rule
 """
 import math
 import struct
+from fractions import Fraction
 
 import numpy as np
 import pytest
@@ -80,6 +81,51 @@ def test_score_is_one_fp32_multiply_and_newest_token_has_elapsed_one():
     hc.pos[idx[-1]] = now[0]
     s2 = oracle.score(hc, now)
     assert s2[idx[-1]] == hc.log_beta[idx[-1]]
+
+
+def nearest_f32(x):
+    """Correct rounding of an exact rational to binary32 (no double rounding)."""
+    c = np.float32(float(x))
+    cands = [c, np.nextafter(c, np.float32(np.inf)), np.nextafter(c, np.float32(-np.inf))]
+    return min(cands, key=lambda v: abs(Fraction(float(v)) - x))
+
+
+@pytest.mark.parametrize("H", [2, 5, 0])
+def test_cached_horizon_tail_gives_the_log_of_the_series_with_one_fused_multiply_add(H):
+    w, hc, now = small_cache([25, 3, 0, 40], salt=20 + H)
+    import torch
+    hc.log_tail = ki.log_tail_of(torch.from_numpy(hc.log_beta), H).numpy()
+    s = oracle.score(hc, now)
+    s64 = oracle.score_horizon(hc, now, H)
+    for e in hc.entry_index():
+        beta = math.exp(float(hc.log_beta[e]))
+        t, i = int(now[0]), int(hc.pos[e])
+        if H > 0:
+            direct = math.fsum(beta ** (sidx - i) for sidx in range(t + 1, t + H + 1))
+        else:
+            direct = beta ** (t + 1 - i) / (1 - beta)
+        assert math.isclose(math.exp(float(s[e])), direct, rel_tol=3e-6)
+        assert math.isclose(float(s[e]), s64[e], rel_tol=2e-6, abs_tol=1e-6)
+        # exactly one rounding: the exact value of elapsed * log_beta + log_tail, rounded once to binary32
+        exact = Fraction(t + 1 - i) * Fraction(float(hc.log_beta[e])) + Fraction(float(hc.log_tail[e]))
+        assert s[e] == nearest_f32(exact), e
+
+
+def test_a_long_horizon_prefers_the_slowly_decaying_old_token():
+    # two entries: A fresh with beta 0.9, B ten steps old with beta 0.985.  One-step score: A 0.9 > B 0.8597;
+    # infinite horizon: A 0.9/0.1 = 9 < B 0.8597/0.015 = 57.3 (Sec. 4.2: longer horizons favour larger beta).
+    w = ki.Workload("t", 0, 1, 1, 2, 2, 64, (0,), (0,), 1, 3.0, 1.5)
+    c, _ = ki.ragged_cache(w, [1, 1], reserve=0)
+    hc = host_cache(w, c)
+    hc.log_beta[:] = np.log(np.array([0.9, 0.985])).astype(np.float32)
+    hc.pos[:] = [9, 0]
+    now = np.array([9], np.int32)
+    keep1, _, _ = oracle.select(hc, oracle.score(hc, now), np.array([1], np.int64))
+    assert keep1[:2].tolist() == [1, 0]
+    import torch
+    hc.log_tail = ki.log_tail_of(torch.from_numpy(hc.log_beta), 0).numpy()
+    keep_inf, _, _ = oracle.select(hc, oracle.score(hc, now), np.array([1], np.int64))
+    assert keep_inf[:2].tolist() == [0, 1]
 
 
 def test_score_decays_monotonically_for_beta_below_one():
