@@ -149,6 +149,22 @@ kvtrim_status kvtrim_decode_attn(kvtrim_ctx *ctx, const kvtrim_cache *c, const v
                                  int32_t layer_begin, int32_t layer_end, float softmax_scale,
                                  float *out, float *lse, void *hip_stream);
 
+/* Retention-gated (soft) attention, Sec. 2.2 - the form the gates are trained with:
+ *   alpha~_i = beta_i^(t-i) e^(z_i) / sum_j beta_j^(t-j) e^(z_j),  o~ = sum_i alpha~_i v_i,
+ * with t = now[seq] (device int32 [n_seq]) the position of the query; beta = 1 gives
+ * kvtrim_decode_attn.  Same arguments, layouts and conventions otherwise; lse is the
+ * log of the weighted denominator. */
+kvtrim_status kvtrim_decode_attn_soft(kvtrim_ctx *ctx, const kvtrim_cache *c, const void *q,
+                                      const int32_t *now, int32_t layer_begin, int32_t layer_end,
+                                      float softmax_scale, float *out, float *lse, void *hip_stream);
+
+/* Expected cache occupancy, the inner sum of the global capacity loss of Sec. 4.1:
+ *   occ_out[seq] = sum over layers, KV heads and cached entries i of beta^(now[seq] - pos_i).
+ * occ_out: device fp64 [n_seq].  Terms are evaluated in fp32 and summed in fp64; the last
+ * bits of the sum depend on the order in which the blocks finish. */
+kvtrim_status kvtrim_occupancy(kvtrim_ctx *ctx, const kvtrim_cache *c, const int32_t *now,
+                               double *occ_out, void *hip_stream);
+
 /* Stages 3 + 4 fused: exactly kvtrim_compact(src -> dst) followed by
  * kvtrim_decode_attn(dst), with the same arguments, results and device-side errors,
  * but every surviving K/V row is read from HBM once: it is used for the attention of
@@ -180,7 +196,7 @@ kvtrim_status kvtrim_append(kvtrim_ctx *ctx, kvtrim_cache *c, const void *k_new,
  * end waits for `hip_stream` and writes, per kernel id, the summed duration in
  * milliseconds and the number of bracketed launches into host arrays of
  * KVTRIM_N_KERNELS elements.  Do not capture a HIP graph while profiling is on. */
-#define KVTRIM_N_KERNELS 14
+#define KVTRIM_N_KERNELS 15
 #define KVTRIM_PROFILE_MAX_LAUNCHES 4096
 kvtrim_status kvtrim_profile_begin(kvtrim_ctx *ctx, uint32_t kernel_mask);
 kvtrim_status kvtrim_profile_end(kvtrim_ctx *ctx, void *hip_stream, double *ms_sum_host,

@@ -160,7 +160,8 @@ def compact(src, keep, dst_cap, reserve):
     return dst
 
 
-def attend(cache, q, scale, layer_begin=0, layer_end=None, want_lse=True):
+def attend(cache, q, scale, layer_begin=0, layer_end=None, want_lse=True, soft_now=None):
+    """Hard-eviction attention; with soft_now (int32 [n_seq]) the retention-gated soft form."""
     sh = cache.shape
     if layer_end is None:
         layer_end = sh.n_layers
@@ -168,9 +169,22 @@ def attend(cache, q, scale, layer_begin=0, layer_end=None, want_lse=True):
     out = np.zeros((sh.n_seq, sh.n_layers, sh.n_q_heads, sh.head_dim), np.float64)
     lse = np.zeros((sh.n_seq, sh.n_layers, sh.n_q_heads), np.float64)
     csh, cc = sh.c(), cache.c()
-    lib().kvo_attend(C.byref(csh), C.byref(cc), _p(q), C.c_int32(layer_begin), C.c_int32(layer_end),
-                     C.c_double(float(scale)), _p(out), _p(lse) if want_lse else None)
+    if soft_now is None:
+        lib().kvo_attend(C.byref(csh), C.byref(cc), _p(q), C.c_int32(layer_begin), C.c_int32(layer_end),
+                         C.c_double(float(scale)), _p(out), _p(lse) if want_lse else None)
+    else:
+        now = np.ascontiguousarray(soft_now, np.int32)
+        lib().kvo_attend_soft(C.byref(csh), C.byref(cc), _p(q), _p(now), C.c_int32(layer_begin),
+                              C.c_int32(layer_end), C.c_double(float(scale)), _p(out), _p(lse) if want_lse else None)
     return out, lse
+
+
+def occupancy(cache, now):
+    now = np.ascontiguousarray(now, np.int32)
+    occ = np.zeros(cache.shape.n_seq, np.float64)
+    sh, cc = cache.shape.c(), cache.c()
+    lib().kvo_occupancy(C.byref(sh), C.byref(cc), _p(now), _p(occ))
+    return occ
 
 
 def append(cache, k_new, v_new, log_beta_new, pos_new, log_tail_new=None):

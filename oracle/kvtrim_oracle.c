@@ -24,6 +24,9 @@
  *                stable filter per segment.                          [pinned]
  *   kvo_attend   Sec. 2.1, Eq. (reform) with r in {0,1}: softmax attention
  *                over the retained entries only, fp64.               [pinned]
+ *   kvo_attend_soft  Sec. 2.2: retention-gated (soft) attention, weights
+ *                beta^(t-i) e^z, fp64.                               [pinned]
+ *   kvo_occupancy    Sec. 4.1: expected occupancy sum of beta^(t-i). [pinned]
  *   kvo_append   bookkeeping: a new token enters every segment's list.
  *
  * Readings of points the paper leaves open (listed again in the design notes):
@@ -239,8 +242,8 @@ int kvo_compact(const kvo_shape *sh, const kvo_cache *src, const uint8_t *keep, 
  * over the entries present in the segment.  q is bf16 [S][L][Hq][D]; out is
  * fp64 [S][L][Hq][D]; lse (optional) is fp64 [S][L][Hq] = log sum_i exp(z_i).
  * Layers outside [layer_begin, layer_end) are not touched. */
-void kvo_attend(const kvo_shape *sh, const kvo_cache *c, const uint16_t *q, int32_t layer_begin,
-                int32_t layer_end, double scale, double *out, double *lse) {
+static void kvo_attend_impl(const kvo_shape *sh, const kvo_cache *c, const uint16_t *q, const int32_t *now,
+                            int32_t layer_begin, int32_t layer_end, double scale, double *out, double *lse) {
     int D = sh->head_dim;
     int G = sh->n_q_heads / sh->n_kv_heads;
 #pragma omp parallel for schedule(dynamic, 1)
@@ -266,6 +269,8 @@ void kvo_attend(const kvo_shape *sh, const kvo_cache *c, const uint16_t *q, int3
                 double dot = 0.0;
                 for (int d = 0; d < D; ++d) dot += bf16_to_f64(qv[d]) * bf16_to_f64(kr[d]);
                 z[i] = dot * scale;
+                if (now) /* retention weight beta^(t-i) as a logit bias (t-i) * log(beta) */
+                    z[i] += (double)(now[seq] - c->pos[c->seg_start[g] + i]) * (double)c->log_beta[c->seg_start[g] + i];
                 if (z[i] > m) m = z[i];
             }
             double denom = 0.0;
@@ -278,6 +283,35 @@ void kvo_attend(const kvo_shape *sh, const kvo_cache *c, const uint16_t *q, int3
             if (lse) lse[hq] = m + log(denom);
         }
         free(z);
+    }
+}
+
+void kvo_attend(const kvo_shape *sh, const kvo_cache *c, const uint16_t *q, int32_t layer_begin,
+                int32_t layer_end, double scale, double *out, double *lse) {
+    kvo_attend_impl(sh, c, q, NULL, layer_begin, layer_end, scale, out, lse);
+}
+
+/* Sec. 2.2, retention-gated attention (the soft form the gates are trained with):
+ *   alpha~_i = beta_i^(t-i) e^(z_i) / sum_j beta_j^(t-j) e^(z_j),   o~ = sum_i alpha~_i v_i,
+ * t = now[seq] the position of the query; same layout and conventions as kvo_attend
+ * (lse is the log of the weighted denominator). */
+void kvo_attend_soft(const kvo_shape *sh, const kvo_cache *c, const uint16_t *q, const int32_t *now,
+                     int32_t layer_begin, int32_t layer_end, double scale, double *out, double *lse) {
+    kvo_attend_impl(sh, c, q, now, layer_begin, layer_end, scale, out, lse);
+}
+
+/* Sec. 4.1, inner sum of the global capacity loss: the expected cache occupancy of a sequence at
+ * step t = now[seq],  occ = sum over its layers, heads and cached entries of beta^(t-i). */
+void kvo_occupancy(const kvo_shape *sh, const kvo_cache *c, const int32_t *now, double *occ_out) {
+    int64_t per_seq = (int64_t)sh->n_layers * sh->n_kv_heads;
+    for (int32_t seq = 0; seq < sh->n_seq; ++seq) {
+        double sum = 0.0;
+        for (int64_t g = seq * per_seq; g < (seq + 1) * per_seq; ++g)
+            for (int32_t j = 0; j < c->seg_len[g]; ++j) {
+                int64_t e = c->seg_start[g] + j;
+                sum += exp((double)(now[seq] - c->pos[e]) * (double)c->log_beta[e]);
+            }
+        occ_out[seq] = sum;
     }
 }
 

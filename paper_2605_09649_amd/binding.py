@@ -13,9 +13,9 @@ STATUS = {0: "KVTRIM_OK", -1: "KVTRIM_EINVAL", -2: "KVTRIM_ENOMEM", -3: "KVTRIM_
 
 EXPORTS = ["kvtrim_create", "kvtrim_destroy", "kvtrim_workspace_bytes", "kvtrim_last_error",
            "kvtrim_poll_error", "kvtrim_score", "kvtrim_select_global", "kvtrim_compact",
-           "kvtrim_decode_attn", "kvtrim_compact_attn", "kvtrim_append", "kvtrim_profile_begin", "kvtrim_profile_end",
+           "kvtrim_decode_attn", "kvtrim_decode_attn_soft", "kvtrim_occupancy", "kvtrim_compact_attn", "kvtrim_append", "kvtrim_profile_begin", "kvtrim_profile_end",
            "kvtrim_kernel_name"]
-N_KERNELS = 14
+N_KERNELS = 15
 
 
 class KvtrimError(RuntimeError):
@@ -60,6 +60,9 @@ def load_library():
                                        C.c_int32, C.c_void_p]
         lib.kvtrim_decode_attn.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_int32, C.c_int32,
                                            C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.kvtrim_decode_attn_soft.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.c_int32,
+                                                C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.kvtrim_occupancy.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.c_void_p]
         lib.kvtrim_compact_attn.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.POINTER(_Cache),
                                             C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p,
                                             C.c_void_p, C.c_void_p]
@@ -196,6 +199,18 @@ def kvtrim_decode_attn(ctx, cache, q, layer_begin, layer_end, softmax_scale, out
                                                   int(layer_begin), int(layer_end), float(softmax_scale),
                                                   _ptr(out, torch.float32), _ptr(lse, torch.float32),
                                                   _stream(stream)), "kvtrim_decode_attn")
+
+
+def kvtrim_decode_attn_soft(ctx, cache, q, now, layer_begin, layer_end, softmax_scale, out, lse=None, stream=None):
+    _check(ctx, load_library().kvtrim_decode_attn_soft(
+        ctx.handle, C.byref(cache.c), _ptr(q, torch.bfloat16), _ptr(now, torch.int32), int(layer_begin),
+        int(layer_end), float(softmax_scale), _ptr(out, torch.float32), _ptr(lse, torch.float32), _stream(stream)),
+        "kvtrim_decode_attn_soft")
+
+
+def kvtrim_occupancy(ctx, cache, now, occ_out, stream=None):
+    _check(ctx, load_library().kvtrim_occupancy(ctx.handle, C.byref(cache.c), _ptr(now, torch.int32),
+                                                _ptr(occ_out, torch.float64), _stream(stream)), "kvtrim_occupancy")
 
 
 def kvtrim_compact_attn(ctx, src, keep, kept, dst, reserve, q, layer_begin, layer_end, softmax_scale, out, lse=None,

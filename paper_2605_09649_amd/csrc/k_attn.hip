@@ -92,10 +92,12 @@ struct PV<G, E, G> {
 };
 
 // partial layout: [chunk][G][D + 2] = (m in base-2 units, l, o[D] unnormalised)
-template <int D, int G>
+// SOFT: retention-gated attention of Sec. 2.2 - the logit of entry i gets the bias (t - i) log(beta_i),
+// t = now[seq] (the weights beta^(t-i) e^z of the soft form); otherwise hard eviction, no bias.
+template <int D, int G, bool SOFT>
 __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const uint16_t* __restrict__ q,
                                                              Shape sh, Workspace ws, int chunk,
-                                                             float scale_log2) {
+                                                             float scale_log2, const int32_t* __restrict__ now) {
     typedef Frag<D> F;
     typedef typename F::vec vec;
     constexpr int E = F::E;
@@ -128,6 +130,7 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
 #pragma unroll
         for (int e = 0; e < E; ++e) o[g][e] = 0.f;
     float m = -INFINITY, l = 0.f;
+    const int t_now = SOFT ? now[seq] : 0;
 
     const vec* kp = reinterpret_cast<const vec*>(c.k);
     const vec* vp = reinterpret_cast<const vec*>(c.v);
@@ -152,7 +155,13 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
         float tmax = -INFINITY;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            z[i] = (r0 + 4 * b4 + i < row_end) ? acc[i] * scale_log2 : -INFINITY;
+            const int row = r0 + 4 * b4 + i;
+            float zi = acc[i] * scale_log2;
+            if (SOFT) {
+                const int64_t e = base + min(row, last);
+                zi = fmaf((float)(t_now - c.pos[e]) * c.log_beta[e], 1.4426950408889634f, zi);
+            }
+            z[i] = row < row_end ? zi : -INFINITY;
             tmax = fmaxf(tmax, z[i]);
         }
         const float m_new = fmaxf(m, tmax);
@@ -322,15 +331,18 @@ __global__ __launch_bounds__(COMB_THREADS) void k_att_combine(Shape sh, Workspac
 
 template <int D, int G>
 static void launch_partial(const CacheView& c, const uint16_t* q, const Shape& sh, const Workspace& ws,
-                           int chunk, float scale_log2, unsigned blocks, hipStream_t st) {
-    hipLaunchKernelGGL((k_att_partial<D, G>), dim3(blocks), dim3(ATT_THREADS), 0, st, c, q, sh, ws, chunk, scale_log2);
+                           int chunk, float scale_log2, const int32_t* now, unsigned blocks, hipStream_t st) {
+    if (now)
+        hipLaunchKernelGGL((k_att_partial<D, G, true>), dim3(blocks), dim3(ATT_THREADS), 0, st, c, q, sh, ws, chunk, scale_log2, now);
+    else
+        hipLaunchKernelGGL((k_att_partial<D, G, false>), dim3(blocks), dim3(ATT_THREADS), 0, st, c, q, sh, ws, chunk, scale_log2, now);
 }
 
 template <int D>
 static bool dispatch_partial(int G, const CacheView& c, const uint16_t* q, const Shape& sh, const Workspace& ws,
-                             int chunk, float scale_log2, unsigned blocks, hipStream_t st) {
+                             int chunk, float scale_log2, const int32_t* now, unsigned blocks, hipStream_t st) {
     switch (G) {
-#define KVTRIM_CASE(g) case g: launch_partial<D, g>(c, q, sh, ws, chunk, scale_log2, blocks, st); return true;
+#define KVTRIM_CASE(g) case g: launch_partial<D, g>(c, q, sh, ws, chunk, scale_log2, now, blocks, st); return true;
         KVTRIM_CASE(1) KVTRIM_CASE(2) KVTRIM_CASE(3) KVTRIM_CASE(4) KVTRIM_CASE(5) KVTRIM_CASE(6) KVTRIM_CASE(7) KVTRIM_CASE(8)
 #undef KVTRIM_CASE
         default: return false;
@@ -342,8 +354,9 @@ int att_chunk_for(const kvtrim_ctx* ctx, int64_t cap) {
     return (int)(chunk < ctx->att_chunk_min ? ctx->att_chunk_min : chunk);
 }
 
-kvtrim_status launch_attn(kvtrim_ctx* ctx, const CacheView& c, const uint16_t* q, int32_t layer_begin,
-                          int32_t layer_end, float scale, float* out, float* lse, hipStream_t st) {
+kvtrim_status launch_attn(kvtrim_ctx* ctx, const CacheView& c, const uint16_t* q, const int32_t* soft_now,
+                          int32_t layer_begin, int32_t layer_end, float scale, float* out, float* lse,
+                          hipStream_t st) {
     const Shape& sh = ctx->shape;
     const Workspace& ws = ctx->ws;
     const int chunk = att_chunk_for(ctx, c.cap);
@@ -355,8 +368,8 @@ kvtrim_status launch_attn(kvtrim_ctx* ctx, const CacheView& c, const uint16_t* q
     {
         ProfScope prof(ctx, K_ATT_PARTIAL, st);
         ok = sh.head_dim == 128
-                  ? dispatch_partial<128>(sh.group, c, q, sh, ws, chunk, scale_log2, (unsigned)max_chunks, st)
-                  : dispatch_partial<64>(sh.group, c, q, sh, ws, chunk, scale_log2, (unsigned)max_chunks, st);
+                  ? dispatch_partial<128>(sh.group, c, q, sh, ws, chunk, scale_log2, soft_now, (unsigned)max_chunks, st)
+                  : dispatch_partial<64>(sh.group, c, q, sh, ws, chunk, scale_log2, soft_now, (unsigned)max_chunks, st);
     }
     if (!ok) return KVTRIM_EINVAL;
     return launch_combine(ctx, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, st);

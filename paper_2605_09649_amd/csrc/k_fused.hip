@@ -303,7 +303,7 @@ kvtrim_status launch_compact_attn(kvtrim_ctx* ctx, const CacheView& src, const u
         CacheView d;
         d.k = dst.k; d.v = dst.v; d.log_beta = dst.log_beta; d.pos = dst.pos;
         d.seg_start = dst.seg_start; d.seg_len = dst.seg_len; d.cap = dst.cap; d.log_tail = dst.log_tail;
-        return launch_attn(ctx, d, q, layer_begin, layer_end, scale, out, lse, st);
+        return launch_attn(ctx, d, q, nullptr, layer_begin, layer_end, scale, out, lse, st);
     }
     launch_cmp_scan(ctx, src, keep, kept, dst, reserve, st);
     bool ok;

@@ -39,6 +39,44 @@ kvtrim_status launch_score(kvtrim_ctx* ctx, const CacheView& c, const int32_t* n
     return KVTRIM_OK;
 }
 
+// Sec. 4.1, inner sum of the global capacity loss: occ[seq] = sum over the cached entries of the
+// sequence of beta^(t - i) = exp((now - pos) log(beta)).  fp32 per entry, fp64 from the wavefront
+// sum on; the blocks add into occ[seq] with fp64 atomics (so the last bits depend on their order).
+__global__ __launch_bounds__(256) void k_occ_zero(double* __restrict__ occ, int n_seq) {
+    for (int i = threadIdx.x; i < n_seq; i += 256) occ[i] = 0.0;
+}
+
+__global__ __launch_bounds__(256) void k_occupancy(CacheView c, const int32_t* __restrict__ now,
+                                                   double* __restrict__ occ, int segs_per_seq, int bps) {
+    __shared__ double lds[17];
+    const int seg = blockIdx.x / bps, part = blockIdx.x % bps;
+    const int len = c.seg_len[seg];
+    const int64_t start = c.seg_start[seg];
+    if (len < 0 || start < 0 || start + len > c.cap) return;     // uniform over the block
+    const int seq = seg / segs_per_seq;
+    const int t = now[seq];
+    const float* lb = c.log_beta + start;
+    const int32_t* pos = c.pos + start;
+    double sum = 0.0;
+    for (int j = part * 256 + threadIdx.x; j < len; j += bps * 256)
+        sum += (double)__builtin_amdgcn_exp2f((float)(t - pos[j]) * lb[j] * 1.4426950408889634f);
+    sum = block_sum<double>(sum, lds);
+    if (threadIdx.x == 0 && sum != 0.0) atomicAdd(&occ[seq], sum);
+}
+
+kvtrim_status launch_occupancy(kvtrim_ctx* ctx, const CacheView& c, const int32_t* now, double* occ,
+                               hipStream_t st) {
+    const Shape& sh = ctx->shape;
+    int64_t bps = c.cap / ((int64_t)sh.nseg * 1024);
+    bps = bps < 1 ? 1 : (bps > 64 ? 64 : bps);
+    ProfScope prof(ctx, K_OCCUPANCY, st);
+    hipLaunchKernelGGL(k_occ_zero, dim3(1), dim3(256), 0, st, occ, sh.n_seq);
+    hipLaunchKernelGGL(k_occupancy, dim3((unsigned)(sh.nseg * bps)), dim3(256), 0, st, c, now, occ,
+                       sh.segs_per_seq, (int)bps);
+    KVTRIM_HIP(ctx, hipGetLastError());
+    return KVTRIM_OK;
+}
+
 // One block per segment: copies the n_new rows behind the segment's end (16 bytes per lane)
 // and the per-entry metadata, then bumps seg_len.  A segment without room is left alone.
 __global__ __launch_bounds__(256) void k_append(CacheViewMut c, const uint16_t* __restrict__ k_new,

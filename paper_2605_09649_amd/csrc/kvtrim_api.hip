@@ -201,7 +201,7 @@ static void free_profile(kvtrim_ctx* ctx) {
 
 static const char* const kernel_names[KVTRIM_N_KERNELS] = {
     "k_score", "k_sel_plan", "k_sel_hist<0>", "k_sel_hist<1>", "k_sel_hist<2>", "k_sel_count", "k_sel_mask",
-    "k_cmp_scan", "k_cmp_copy", "k_att_plan", "k_att_partial", "k_att_combine", "k_append", "k_cmp_attn"};
+    "k_cmp_scan", "k_cmp_copy", "k_att_plan", "k_att_partial", "k_att_combine", "k_append", "k_cmp_attn", "k_occupancy"};
 
 const char* kvtrim_kernel_name(int32_t id) { return id >= 0 && id < KVTRIM_N_KERNELS ? kernel_names[id] : nullptr; }
 
@@ -316,8 +316,30 @@ kvtrim_status kvtrim_decode_attn(kvtrim_ctx* ctx, const kvtrim_cache* c, const v
     if (layer_begin < 0 || layer_end > ctx->cfg.n_layers || layer_begin >= layer_end)
         return invalid(ctx, "empty or out-of-range layer range");
     if (!(softmax_scale == softmax_scale)) return invalid(ctx, "softmax_scale is NaN");
-    return launch_attn(ctx, view_of(c), (const uint16_t*)q, layer_begin, layer_end, softmax_scale, out, lse,
+    return launch_attn(ctx, view_of(c), (const uint16_t*)q, nullptr, layer_begin, layer_end, softmax_scale, out, lse,
                        (hipStream_t)hip_stream);
+}
+
+kvtrim_status kvtrim_decode_attn_soft(kvtrim_ctx* ctx, const kvtrim_cache* c, const void* q, const int32_t* now,
+                                      int32_t layer_begin, int32_t layer_end, float softmax_scale, float* out,
+                                      float* lse, void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    if (const char* p = cache_problem(ctx, c, true)) return invalid(ctx, p);
+    if (!q || !out || !now) return invalid(ctx, "q / out / now is NULL");
+    if (((uintptr_t)q) & 15) return invalid(ctx, "q not 16-byte aligned");
+    if (layer_begin < 0 || layer_end > ctx->cfg.n_layers || layer_begin >= layer_end)
+        return invalid(ctx, "empty or out-of-range layer range");
+    if (!(softmax_scale == softmax_scale)) return invalid(ctx, "softmax_scale is NaN");
+    return launch_attn(ctx, view_of(c), (const uint16_t*)q, now, layer_begin, layer_end, softmax_scale, out, lse,
+                       (hipStream_t)hip_stream);
+}
+
+kvtrim_status kvtrim_occupancy(kvtrim_ctx* ctx, const kvtrim_cache* c, const int32_t* now, double* occ_out,
+                               void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    if (const char* p = cache_problem(ctx, c, false)) return invalid(ctx, p);
+    if (!now || !occ_out) return invalid(ctx, "now / occ_out is NULL");
+    return launch_occupancy(ctx, view_of(c), now, occ_out, (hipStream_t)hip_stream);
 }
 
 kvtrim_status kvtrim_compact_attn(kvtrim_ctx* ctx, const kvtrim_cache* src, const uint8_t* keep, const int32_t* kept,

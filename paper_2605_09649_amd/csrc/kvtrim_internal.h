@@ -98,7 +98,7 @@ struct Workspace {
 namespace kvtrim {
 enum KernelId {
     K_SCORE = 0, K_SEL_PLAN, K_SEL_HIST0, K_SEL_HIST1, K_SEL_HIST2, K_SEL_COUNT, K_SEL_MASK,
-    K_CMP_SCAN, K_CMP_COPY, K_ATT_PLAN, K_ATT_PARTIAL, K_ATT_COMBINE, K_APPEND, K_CMP_ATTN, K_COUNT
+    K_CMP_SCAN, K_CMP_COPY, K_ATT_PLAN, K_ATT_PARTIAL, K_ATT_COMBINE, K_APPEND, K_CMP_ATTN, K_OCCUPANCY, K_COUNT
 };
 static_assert(K_COUNT == KVTRIM_N_KERNELS, "kernel table out of step with the header");
 }  // namespace kvtrim
@@ -130,8 +130,9 @@ kvtrim_status launch_select(kvtrim_ctx*, const CacheView&, const float* score, c
                             uint8_t* keep, int32_t* kept, uint32_t* thr, hipStream_t);
 kvtrim_status launch_compact(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const int32_t* kept,
                              const CacheViewMut& dst, int32_t reserve, hipStream_t);
-kvtrim_status launch_attn(kvtrim_ctx*, const CacheView&, const uint16_t* q, int32_t layer_begin,
-                          int32_t layer_end, float scale, float* out, float* lse, hipStream_t);
+kvtrim_status launch_attn(kvtrim_ctx*, const CacheView&, const uint16_t* q, const int32_t* soft_now,
+                          int32_t layer_begin, int32_t layer_end, float scale, float* out, float* lse, hipStream_t);
+kvtrim_status launch_occupancy(kvtrim_ctx*, const CacheView&, const int32_t* now, double* occ, hipStream_t);
 void launch_cmp_scan(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const int32_t* kept,
                      const CacheViewMut& dst, int32_t reserve, hipStream_t);
 kvtrim_status launch_combine(kvtrim_ctx*, const int32_t* chunk_prefix, int32_t layer_begin, int32_t layer_end,

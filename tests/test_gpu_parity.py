@@ -326,3 +326,45 @@ def test_results_are_deterministic_across_runs():
     b = run_steps_both(w, steps=2, budget=w.budget, device=DEV)
     check(a)
     assert [r["attn_err"] for r in a] == [r["attn_err"] for r in b]
+
+
+# ---------------------------------------------------------------------------------- soft attention, occupancy
+
+@pytest.mark.parametrize("D,G,S", [(128, 4, 1), (64, 2, 2), (128, 7, 2)])
+def test_soft_retention_gated_attention_and_occupancy(D, G, S):
+    w = wl(S, 2, 2, G, D)
+    rng = np.random.default_rng(D + G + S)
+    seg_len = rng.integers(0, 1800, w.nseg)
+    seg_len[1] = 0
+    c, now = ki.ragged_cache(w, seg_len, salt=40 + G)
+    hc = host_cache(w, c)
+    dc = kv.Cache.from_dict(c, DEV)
+    ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, D, hc.cap)
+    q = ki.decode_inputs(w, 2)["q"]
+    scale = 1.0 / math.sqrt(D)
+    now_np = now.numpy() + 3
+    ref, ref_lse = oracle.attend(hc, bf16_bits(q), scale, soft_now=now_np)
+    out = torch.full(ref.shape, 99.0, dtype=torch.float32, device=DEV)
+    lse = torch.full(ref_lse.shape, 99.0, dtype=torch.float32, device=DEV)
+    now_dev = torch.from_numpy(now_np).to(DEV)
+    kv.kvtrim_decode_attn_soft(ctx, dc, q.to(DEV), now_dev, 0, w.n_layers, scale, out, lse)
+    assert kv.kvtrim_poll_error(ctx) == 0
+    assert attn_error(out.cpu().numpy(), ref) <= ATTN_TOL
+    fin = np.isfinite(ref_lse)
+    assert np.abs(lse.cpu().numpy()[fin] - ref_lse[fin]).max() <= 2e-3
+    assert np.array_equal(np.isneginf(lse.cpu().numpy()), np.isneginf(ref_lse))
+    # the soft form differs from the hard one on this input, and beta = 1 makes them coincide
+    hard, _ = oracle.attend(hc, bf16_bits(q), scale)
+    assert attn_error(out.cpu().numpy(), hard) > 10 * ATTN_TOL
+    ones = dict(c)
+    ones["log_beta"] = torch.zeros_like(c["log_beta"])
+    out1 = torch.zeros_like(out)
+    out2 = torch.zeros_like(out)
+    d1 = kv.Cache.from_dict(ones, DEV)
+    kv.kvtrim_decode_attn_soft(ctx, d1, q.to(DEV), now_dev, 0, w.n_layers, scale, out1)
+    kv.kvtrim_decode_attn(ctx, d1, q.to(DEV), 0, w.n_layers, scale, out2)
+    assert torch.equal(out1, out2)
+    # occupancy
+    occ = torch.zeros(S, dtype=torch.float64, device=DEV)
+    kv.kvtrim_occupancy(ctx, dc, now_dev, occ)
+    np.testing.assert_allclose(occ.cpu().numpy(), oracle.occupancy(hc, now_np), rtol=2e-6)

@@ -200,3 +200,91 @@ def test_hard_eviction_satisfies_the_dilution_identity():
         delta_r = 1.0 - evicted[0, 0, j, 0]
         ratio = rho_d / rho_u
         assert math.isclose(delta_r, ratio * delta / ((1 - delta) + ratio * delta), rel_tol=1e-10)
+
+
+# ----------------------------------------------------------------------------- soft (retention-gated) attention, occupancy
+
+def test_soft_attention_equals_library_sdpa_with_an_additive_bias():
+    # Sec. 2.2: weights beta^(t-i) e^z, i.e. logits z + (t-i) log(beta); torch SDPA takes that as a float mask
+    w, hc, now = make([40, 0, 23, 9], S=1, L=2, H=2, G=2, D=64, salt=31)
+    q = rand_q(w, 4)
+    scale = 0.125
+    out, lse = oracle.attend(hc, q, scale, soft_now=now)
+    qf = bits_to_f64(q).reshape(1, 2, 4, 64)
+    for l in range(2):
+        for h in range(2):
+            g = w.seg_id(0, l, h)
+            s0, n = int(hc.seg_start[g]), int(hc.seg_len[g])
+            if n == 0:
+                assert np.all(out[0, l, h * 2:(h + 1) * 2] == 0)
+                continue
+            K = torch.from_numpy(bits_to_f64(hc.k[s0:s0 + n]))
+            V = torch.from_numpy(bits_to_f64(hc.v[s0:s0 + n]))
+            Q = torch.from_numpy(qf[0, l, h * 2:(h + 1) * 2])
+            bias = torch.from_numpy((now[0] - hc.pos[s0:s0 + n]).astype(np.float64) * hc.log_beta[s0:s0 + n].astype(np.float64))
+            o = torch.nn.functional.scaled_dot_product_attention(Q[None], K[None], V[None], attn_mask=bias[None, None, :].expand(1, 2, n),
+                                                                 scale=scale)
+            np.testing.assert_allclose(out[0, l, h * 2:(h + 1) * 2], o[0].numpy(), rtol=1e-11, atol=1e-13)
+            np.testing.assert_allclose(lse[0, l, h * 2:(h + 1) * 2],
+                                       torch.logsumexp(Q @ K.T * scale + bias[None, :], dim=-1).numpy(), rtol=1e-12)
+
+
+def test_soft_attention_with_beta_one_is_standard_attention():
+    # Sec. 2.2: beta_i = 1 recovers standard attention
+    w, hc, now = make([30, 12, 7, 21], salt=32)
+    hc.log_beta[:] = 0.0
+    q = rand_q(w, 6)
+    hard, hard_lse = oracle.attend(hc, q, 0.125)
+    soft, soft_lse = oracle.attend(hc, q, 0.125, soft_now=now)
+    np.testing.assert_array_equal(soft, hard)
+    np.testing.assert_array_equal(soft_lse, hard_lse)
+
+
+def test_soft_retention_weights_satisfy_the_dilution_identity():
+    # Cor. 3.2 holds for general retention weights r in [0,1], here r_i = beta_i^(t-i)
+    n = 48
+    w, hc, now = make([n], L=1, H=1, G=2, salt=33)
+    rng = np.random.default_rng(9)
+    s0 = int(hc.seg_start[0])
+    useful = rng.random(n) < 0.3
+    hc.v[s0:s0 + n, 0] = np.where(useful, 0x3F80, 0x0000)          # bf16 1.0 / 0.0: V[:,0] = indicator of U
+    q = rand_q(w, 8)
+    scale = 0.125
+    full, _ = oracle.attend(hc, q, scale)
+    soft, _ = oracle.attend(hc, q, scale, soft_now=now)
+    r = np.exp((now[0] - hc.pos[s0:s0 + n]).astype(np.float64) * hc.log_beta[s0:s0 + n].astype(np.float64))
+    K = bits_to_f64(hc.k[s0:s0 + n])
+    for j in range(2):
+        z = K @ bits_to_f64(q.reshape(-1, 64)[j]) * scale
+        ez = np.exp(z - z.max())
+        rho_u = (r[useful] * ez[useful]).sum() / ez[useful].sum()
+        rho_d = (r[~useful] * ez[~useful]).sum() / ez[~useful].sum()
+        delta, delta_r = 1.0 - full[0, 0, j, 0], 1.0 - soft[0, 0, j, 0]
+        ratio = rho_d / rho_u
+        assert math.isclose(delta_r, ratio * delta / ((1 - delta) + ratio * delta), rel_tol=1e-10)
+
+
+def test_occupancy_closed_forms():
+    # equal beta and positions 0..T-1: sum_{i<T} beta^(t-i) is a geometric series; beta = 1 counts the entries
+    L, H, T = 2, 3, 40
+    w = ki.Workload("t", 0, 1, L, H, 2 * H, 64, (T,), (0,), 1, 3.0, 1.5)
+    hc = host_cache(w, ki.prefill_cache(w, reserve=1))
+    beta = 0.93
+    hc.log_beta[:] = np.float32(math.log(beta))
+    b = math.exp(float(np.float32(math.log(beta))))
+    t = T + 4
+    occ = oracle.occupancy(hc, np.array([t], np.int32))
+    closed = L * H * b ** (t - T + 1) * (1 - b ** T) / (1 - b)
+    assert math.isclose(occ[0], closed, rel_tol=1e-12)
+    hc.log_beta[:] = 0.0
+    assert oracle.occupancy(hc, np.array([t], np.int32))[0] == L * H * T
+    # per sequence
+    w2, hc2, now2 = make(np.arange(8) + 1, S=2, L=2, H=2, salt=34)
+    occ2 = oracle.occupancy(hc2, now2)
+    for s in range(2):
+        tot = 0.0
+        for g in range(s * 4, (s + 1) * 4):
+            for j in range(hc2.seg_len[g]):
+                e = hc2.seg_start[g] + j
+                tot += math.exp(float(now2[s] - hc2.pos[e]) * float(hc2.log_beta[e]))
+        assert math.isclose(occ2[s], tot, rel_tol=1e-12)
