@@ -187,6 +187,80 @@ kvtrim_status kvtrim_append(kvtrim_ctx *ctx, kvtrim_cache *c, const void *k_new,
                             const float *log_beta_new, const float *log_tail_new, const int32_t *pos_new,
                             int32_t n_new, void *hip_stream);
 
+/* ------------------------------------------------------------------------------------
+ * Paged variant: the layout of Sec. 4.2 "Implementation details" itself.  KV entries live
+ * in fixed-size pages of KVTRIM_PAGE_SIZE slots; every (sequence, layer, KV head) segment
+ * owns a list of pages (its block table) and so has its own variable length; evicting an
+ * entry frees its slot and moves no K/V.  The order of the entries inside a segment is
+ * arbitrary (attention does not depend on it); the selection still breaks ties by
+ * (layer, head, position), using the stored positions.
+ *
+ *   k, v         bf16 [n_pages][KVTRIM_PAGE_SIZE][head_dim]
+ *   log_beta     fp32 [n_pages][KVTRIM_PAGE_SIZE]
+ *   pos          int32 [n_pages][KVTRIM_PAGE_SIZE]; a negative value marks an empty slot
+ *   log_tail     fp32 [n_pages][KVTRIM_PAGE_SIZE] or NULL (lookahead horizon, as above)
+ *   block_table  int32 [nseg][max_pages_per_seg]  pages of each segment (first seg_pages[g] valid)
+ *   seg_pages    int32 [nseg]      pages in the segment's table
+ *   seg_live     int32 [nseg]      live entries of the segment
+ *   page_owner   int32 [n_pages]   owning segment, negative = free
+ *   page_live    int32 [n_pages]   live entries in the page
+ *   free_list    int32 [n_pages]   stack of free page ids; n_free int32 [1] its height
+ * All of it is caller-owned device memory; kvtrim_paged_build initialises the bookkeeping.
+ * Slot s of page p is entry p*KVTRIM_PAGE_SIZE + s of the flat score / keep arrays.
+ * n_pages * KVTRIM_PAGE_SIZE must not exceed the context's max_entries, and the calls that run
+ * attention need n_pages <= 32768. */
+#define KVTRIM_PAGE_SIZE 128
+typedef struct {
+    void *k;
+    void *v;
+    float *log_beta;
+    int32_t *pos;
+    float *log_tail;
+    int32_t *block_table;
+    int32_t *seg_pages;
+    int32_t *seg_live;
+    int32_t *page_owner;
+    int32_t *page_live;
+    int32_t *free_list;
+    int32_t *n_free;
+    int32_t n_pages;
+    int32_t max_pages_per_seg;
+} kvtrim_paged_cache;
+
+/* First compression (Fig. "Prefill/compression"): the entries of the ragged cache `src` with
+ * keep[e] != 0 (keep, kept as produced by kvtrim_select_global) are gathered, in order, into
+ * consecutive pages per segment; the remaining pages go to the free list.  Device-side errors:
+ * KVTRIM_ECAP (not enough pages, or a segment needs more than max_pages_per_seg),
+ * KVTRIM_EMISMATCH as in kvtrim_compact. */
+kvtrim_status kvtrim_paged_build(kvtrim_ctx *ctx, const kvtrim_cache *src, const uint8_t *keep,
+                                 const int32_t *kept, kvtrim_paged_cache *dst, void *hip_stream);
+
+/* One new token per segment (k_new, v_new: bf16 [nseg][head_dim]; log_beta_new, pos_new:
+ * [nseg]; log_tail_new iff the cache carries log_tail): it takes an empty slot of the
+ * segment's pages, or the first slot of a page from the free list.  KVTRIM_ECAP when no page is
+ * free or the block table is full (that segment is then left unchanged). */
+kvtrim_status kvtrim_paged_append(kvtrim_ctx *ctx, kvtrim_paged_cache *c, const void *k_new, const void *v_new,
+                                  const float *log_beta_new, const float *log_tail_new, const int32_t *pos_new,
+                                  void *hip_stream);
+
+/* Stage 1 on the paged layout: score_out fp32 [n_pages * KVTRIM_PAGE_SIZE], written for live slots. */
+kvtrim_status kvtrim_paged_score(kvtrim_ctx *ctx, const kvtrim_paged_cache *c, const int32_t *now,
+                                 float *score_out, void *hip_stream);
+
+/* Stage 2 on the paged layout: same rule and outputs as kvtrim_select_global; keep_out uint8
+ * [n_pages * KVTRIM_PAGE_SIZE] is written for live slots. */
+kvtrim_status kvtrim_paged_select(kvtrim_ctx *ctx, const kvtrim_paged_cache *c, const float *score,
+                                  const int64_t *budget, uint8_t *keep_out, int32_t *kept_out,
+                                  uint32_t *thr_key_out, void *hip_stream);
+
+/* Stage 3 on the paged layout: live slots with keep[e] == 0 become empty; pages left without a
+ * live entry return to the free list and leave their segment's block table.  No K/V moves. */
+kvtrim_status kvtrim_paged_evict(kvtrim_ctx *ctx, kvtrim_paged_cache *c, const uint8_t *keep, void *hip_stream);
+
+/* Stage 4 on the paged layout: as kvtrim_decode_attn, over the live slots of each segment's pages. */
+kvtrim_status kvtrim_paged_attn(kvtrim_ctx *ctx, const kvtrim_paged_cache *c, const void *q, int32_t layer_begin,
+                                int32_t layer_end, float softmax_scale, float *out, float *lse, void *hip_stream);
+
 /* Instrumentation (for the benchmark; not a step of the method).  Between
  * kvtrim_profile_begin and kvtrim_profile_end every launch of a kernel whose bit is
  * set in `kernel_mask` (bit i = kernel id i, names from kvtrim_kernel_name) is
@@ -196,7 +270,7 @@ kvtrim_status kvtrim_append(kvtrim_ctx *ctx, kvtrim_cache *c, const void *k_new,
  * end waits for `hip_stream` and writes, per kernel id, the summed duration in
  * milliseconds and the number of bracketed launches into host arrays of
  * KVTRIM_N_KERNELS elements.  Do not capture a HIP graph while profiling is on. */
-#define KVTRIM_N_KERNELS 15
+#define KVTRIM_N_KERNELS 23
 #define KVTRIM_PROFILE_MAX_LAUNCHES 4096
 kvtrim_status kvtrim_profile_begin(kvtrim_ctx *ctx, uint32_t kernel_mask);
 kvtrim_status kvtrim_profile_end(kvtrim_ctx *ctx, void *hip_stream, double *ms_sum_host,

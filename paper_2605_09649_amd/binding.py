@@ -13,9 +13,12 @@ STATUS = {0: "KVTRIM_OK", -1: "KVTRIM_EINVAL", -2: "KVTRIM_ENOMEM", -3: "KVTRIM_
 
 EXPORTS = ["kvtrim_create", "kvtrim_destroy", "kvtrim_workspace_bytes", "kvtrim_last_error",
            "kvtrim_poll_error", "kvtrim_score", "kvtrim_select_global", "kvtrim_compact",
-           "kvtrim_decode_attn", "kvtrim_decode_attn_soft", "kvtrim_occupancy", "kvtrim_compact_attn", "kvtrim_append", "kvtrim_profile_begin", "kvtrim_profile_end",
+           "kvtrim_decode_attn", "kvtrim_decode_attn_soft", "kvtrim_occupancy", "kvtrim_compact_attn", "kvtrim_append",
+           "kvtrim_paged_build", "kvtrim_paged_append", "kvtrim_paged_score", "kvtrim_paged_select",
+           "kvtrim_paged_evict", "kvtrim_paged_attn", "kvtrim_profile_begin", "kvtrim_profile_end",
            "kvtrim_kernel_name"]
-N_KERNELS = 15
+PAGE_SIZE = 128
+N_KERNELS = 23
 
 
 class KvtrimError(RuntimeError):
@@ -33,6 +36,14 @@ class _Cache(C.Structure):
     _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("log_beta", C.c_void_p), ("pos", C.c_void_p),
                 ("seg_start", C.c_void_p), ("seg_len", C.c_void_p), ("cap_entries", C.c_int64),
                 ("log_tail", C.c_void_p)]
+
+
+class _PagedCache(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("log_beta", C.c_void_p), ("pos", C.c_void_p),
+                ("log_tail", C.c_void_p), ("block_table", C.c_void_p), ("seg_pages", C.c_void_p),
+                ("seg_live", C.c_void_p), ("page_owner", C.c_void_p), ("page_live", C.c_void_p),
+                ("free_list", C.c_void_p), ("n_free", C.c_void_p), ("n_pages", C.c_int32),
+                ("max_pages_per_seg", C.c_int32)]
 
 
 def library_path():
@@ -68,6 +79,16 @@ def load_library():
                                             C.c_void_p, C.c_void_p]
         lib.kvtrim_append.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+        P = C.POINTER(_PagedCache)
+        lib.kvtrim_paged_build.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_void_p, P, C.c_void_p]
+        lib.kvtrim_paged_append.argtypes = [C.c_void_p, P, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_void_p]
+        lib.kvtrim_paged_score.argtypes = [C.c_void_p, P, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.kvtrim_paged_select.argtypes = [C.c_void_p, P, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_void_p]
+        lib.kvtrim_paged_evict.argtypes = [C.c_void_p, P, C.c_void_p, C.c_void_p]
+        lib.kvtrim_paged_attn.argtypes = [C.c_void_p, P, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p,
+                                          C.c_void_p, C.c_void_p]
         lib.kvtrim_profile_begin.argtypes = [C.c_void_p, C.c_uint32]
         lib.kvtrim_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         lib.kvtrim_kernel_name.argtypes = [C.c_int32]
@@ -131,6 +152,34 @@ class Cache:
                    torch.zeros(nseg, dtype=torch.int64, device=device),
                    torch.zeros(nseg, dtype=torch.int32, device=device),
                    torch.zeros(cap, dtype=torch.float32, device=device) if with_tail else None)
+
+
+class PagedCache:
+    """Paged cache: a pool of PAGE_SIZE-slot pages, block tables and the free-page stack (device
+    tensors) plus the C view of them.  kvtrim_paged_build fills in the bookkeeping."""
+
+    def __init__(self, nseg, head_dim, n_pages, max_pages_per_seg, device="cuda", with_tail=False):
+        n = n_pages * PAGE_SIZE
+        i32 = dict(dtype=torch.int32, device=device)
+        self.n_pages, self.max_pages_per_seg, self.nseg = int(n_pages), int(max_pages_per_seg), int(nseg)
+        self.k = torch.zeros(n, head_dim, dtype=torch.bfloat16, device=device)
+        self.v = torch.zeros(n, head_dim, dtype=torch.bfloat16, device=device)
+        self.log_beta = torch.zeros(n, dtype=torch.float32, device=device)
+        self.pos = torch.full((n,), -1, **i32)
+        self.log_tail = torch.zeros(n, dtype=torch.float32, device=device) if with_tail else None
+        self.block_table = torch.zeros(nseg, max_pages_per_seg, **i32)
+        self.seg_pages = torch.zeros(nseg, **i32)
+        self.seg_live = torch.zeros(nseg, **i32)
+        self.page_owner = torch.full((n_pages,), -1, **i32)
+        self.page_live = torch.zeros(n_pages, **i32)
+        self.free_list = torch.zeros(n_pages, **i32)
+        self.n_free = torch.zeros(1, **i32)
+        self.slots = n
+        self.c = _PagedCache(_ptr(self.k).value, _ptr(self.v).value, _ptr(self.log_beta).value, _ptr(self.pos).value,
+                             None if self.log_tail is None else _ptr(self.log_tail).value,
+                             _ptr(self.block_table).value, _ptr(self.seg_pages).value, _ptr(self.seg_live).value,
+                             _ptr(self.page_owner).value, _ptr(self.page_live).value, _ptr(self.free_list).value,
+                             _ptr(self.n_free).value, self.n_pages, self.max_pages_per_seg)
 
 
 class Context:
@@ -227,6 +276,44 @@ def kvtrim_append(ctx, cache, k_new, v_new, log_beta_new, pos_new, n_new, log_ta
                                              _ptr(log_tail_new, torch.float32), _ptr(pos_new, torch.int32),
                                              int(n_new), _stream(stream)),
            "kvtrim_append")
+
+
+def kvtrim_paged_build(ctx, src, keep, kept, dst, stream=None):
+    _check(ctx, load_library().kvtrim_paged_build(ctx.handle, C.byref(src.c), _ptr(keep, torch.uint8),
+                                                  _ptr(kept, torch.int32), C.byref(dst.c), _stream(stream)),
+           "kvtrim_paged_build")
+
+
+def kvtrim_paged_append(ctx, cache, k_new, v_new, log_beta_new, pos_new, log_tail_new=None, stream=None):
+    _check(ctx, load_library().kvtrim_paged_append(
+        ctx.handle, C.byref(cache.c), _ptr(k_new, torch.bfloat16), _ptr(v_new, torch.bfloat16),
+        _ptr(log_beta_new, torch.float32), _ptr(log_tail_new, torch.float32), _ptr(pos_new, torch.int32),
+        _stream(stream)), "kvtrim_paged_append")
+
+
+def kvtrim_paged_score(ctx, cache, now, score_out, stream=None):
+    _check(ctx, load_library().kvtrim_paged_score(ctx.handle, C.byref(cache.c), _ptr(now, torch.int32),
+                                                  _ptr(score_out, torch.float32), _stream(stream)),
+           "kvtrim_paged_score")
+
+
+def kvtrim_paged_select(ctx, cache, score, budget, keep_out, kept_out, thr_key_out=None, stream=None):
+    _check(ctx, load_library().kvtrim_paged_select(
+        ctx.handle, C.byref(cache.c), _ptr(score, torch.float32), _ptr(budget, torch.int64),
+        _ptr(keep_out, torch.uint8), _ptr(kept_out, torch.int32), _ptr(thr_key_out), _stream(stream)),
+        "kvtrim_paged_select")
+
+
+def kvtrim_paged_evict(ctx, cache, keep, stream=None):
+    _check(ctx, load_library().kvtrim_paged_evict(ctx.handle, C.byref(cache.c), _ptr(keep, torch.uint8),
+                                                  _stream(stream)), "kvtrim_paged_evict")
+
+
+def kvtrim_paged_attn(ctx, cache, q, layer_begin, layer_end, softmax_scale, out, lse=None, stream=None):
+    _check(ctx, load_library().kvtrim_paged_attn(ctx.handle, C.byref(cache.c), _ptr(q, torch.bfloat16),
+                                                 int(layer_begin), int(layer_end), float(softmax_scale),
+                                                 _ptr(out, torch.float32), _ptr(lse, torch.float32),
+                                                 _stream(stream)), "kvtrim_paged_attn")
 
 
 def kvtrim_kernel_name(kernel_id):

@@ -94,7 +94,9 @@ struct PV<G, E, G> {
 // partial layout: [chunk][G][D + 2] = (m in base-2 units, l, o[D] unnormalised)
 // SOFT: retention-gated attention of Sec. 2.2 - the logit of entry i gets the bias (t - i) log(beta_i),
 // t = now[seq] (the weights beta^(t-i) e^z of the soft form); otherwise hard eviction, no bias.
-template <int D, int G, bool SOFT>
+// PAGED: the chunk is a page of a paged cache; slots with a negative position are empty and take no
+// part (their logit is -inf and their V row, which may hold anything, is replaced by zeros).
+template <int D, int G, bool SOFT, bool PAGED>
 __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const uint16_t* __restrict__ q,
                                                              Shape sh, Workspace ws, int chunk,
                                                              float scale_log2, const int32_t* __restrict__ now) {
@@ -156,12 +158,15 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int row = r0 + 4 * b4 + i;
+            const int64_t e = base + min(row, last);
             float zi = acc[i] * scale_log2;
-            if (SOFT) {
-                const int64_t e = base + min(row, last);
-                zi = fmaf((float)(t_now - c.pos[e]) * c.log_beta[e], 1.4426950408889634f, zi);
+            if (SOFT) zi = fmaf((float)(t_now - c.pos[e]) * c.log_beta[e], 1.4426950408889634f, zi);
+            bool valid = row < row_end;
+            if (PAGED) {
+                valid = valid && c.pos[e] >= 0;
+                if (!valid) vf[i] = F::zero();
             }
-            z[i] = row < row_end ? zi : -INFINITY;
+            z[i] = valid ? zi : -INFINITY;
             tmax = fmaxf(tmax, z[i]);
         }
         const float m_new = fmaxf(m, tmax);
@@ -331,18 +336,22 @@ __global__ __launch_bounds__(COMB_THREADS) void k_att_combine(Shape sh, Workspac
 
 template <int D, int G>
 static void launch_partial(const CacheView& c, const uint16_t* q, const Shape& sh, const Workspace& ws,
-                           int chunk, float scale_log2, const int32_t* now, unsigned blocks, hipStream_t st) {
-    if (now)
-        hipLaunchKernelGGL((k_att_partial<D, G, true>), dim3(blocks), dim3(ATT_THREADS), 0, st, c, q, sh, ws, chunk, scale_log2, now);
+                           int chunk, float scale_log2, const int32_t* now, bool paged, unsigned blocks,
+                           hipStream_t st) {
+    if (paged)
+        hipLaunchKernelGGL((k_att_partial<D, G, false, true>), dim3(blocks), dim3(ATT_THREADS), 0, st, c, q, sh, ws, chunk, scale_log2, now);
+    else if (now)
+        hipLaunchKernelGGL((k_att_partial<D, G, true, false>), dim3(blocks), dim3(ATT_THREADS), 0, st, c, q, sh, ws, chunk, scale_log2, now);
     else
-        hipLaunchKernelGGL((k_att_partial<D, G, false>), dim3(blocks), dim3(ATT_THREADS), 0, st, c, q, sh, ws, chunk, scale_log2, now);
+        hipLaunchKernelGGL((k_att_partial<D, G, false, false>), dim3(blocks), dim3(ATT_THREADS), 0, st, c, q, sh, ws, chunk, scale_log2, now);
 }
 
 template <int D>
 static bool dispatch_partial(int G, const CacheView& c, const uint16_t* q, const Shape& sh, const Workspace& ws,
-                             int chunk, float scale_log2, const int32_t* now, unsigned blocks, hipStream_t st) {
+                             int chunk, float scale_log2, const int32_t* now, bool paged, unsigned blocks,
+                             hipStream_t st) {
     switch (G) {
-#define KVTRIM_CASE(g) case g: launch_partial<D, g>(c, q, sh, ws, chunk, scale_log2, now, blocks, st); return true;
+#define KVTRIM_CASE(g) case g: launch_partial<D, g>(c, q, sh, ws, chunk, scale_log2, now, paged, blocks, st); return true;
         KVTRIM_CASE(1) KVTRIM_CASE(2) KVTRIM_CASE(3) KVTRIM_CASE(4) KVTRIM_CASE(5) KVTRIM_CASE(6) KVTRIM_CASE(7) KVTRIM_CASE(8)
 #undef KVTRIM_CASE
         default: return false;
@@ -368,8 +377,27 @@ kvtrim_status launch_attn(kvtrim_ctx* ctx, const CacheView& c, const uint16_t* q
     {
         ProfScope prof(ctx, K_ATT_PARTIAL, st);
         ok = sh.head_dim == 128
-                  ? dispatch_partial<128>(sh.group, c, q, sh, ws, chunk, scale_log2, soft_now, (unsigned)max_chunks, st)
-                  : dispatch_partial<64>(sh.group, c, q, sh, ws, chunk, scale_log2, soft_now, (unsigned)max_chunks, st);
+                  ? dispatch_partial<128>(sh.group, c, q, sh, ws, chunk, scale_log2, soft_now, false, (unsigned)max_chunks, st)
+                  : dispatch_partial<64>(sh.group, c, q, sh, ws, chunk, scale_log2, soft_now, false, (unsigned)max_chunks, st);
+    }
+    if (!ok) return KVTRIM_EINVAL;
+    return launch_combine(ctx, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, st);
+}
+
+// Attention over the pages listed in ws.att_desc / ws.att_chunk_prefix (built by the paged plan
+// kernel): one block per page, then the per-segment merge.
+kvtrim_status launch_attn_paged(kvtrim_ctx* ctx, const CacheView& pool, const uint16_t* q, int n_pages,
+                                int32_t layer_begin, int32_t layer_end, float scale, float* out, float* lse,
+                                hipStream_t st) {
+    const Shape& sh = ctx->shape;
+    const Workspace& ws = ctx->ws;
+    const float scale_log2 = scale * 1.4426950408889634f;
+    bool ok;
+    {
+        ProfScope prof(ctx, K_ATT_PARTIAL, st);
+        ok = sh.head_dim == 128
+                 ? dispatch_partial<128>(sh.group, pool, q, sh, ws, KVTRIM_PAGE_SIZE, scale_log2, nullptr, true, (unsigned)n_pages, st)
+                 : dispatch_partial<64>(sh.group, pool, q, sh, ws, KVTRIM_PAGE_SIZE, scale_log2, nullptr, true, (unsigned)n_pages, st);
     }
     if (!ok) return KVTRIM_EINVAL;
     return launch_combine(ctx, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, st);

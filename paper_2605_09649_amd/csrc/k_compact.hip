@@ -36,7 +36,7 @@ __device__ __forceinline__ void block_sum_n(int64_t (&v)[N], int64_t* lds /* [16
 
 __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const uint8_t* __restrict__ keep,
                                                            const int32_t* __restrict__ kept, CacheViewMut dst,
-                                                           int reserve, Shape sh, Workspace ws) {
+                                                           int reserve, int align, Shape sh, Workspace ws) {
     __shared__ int64_t lds64[17];
     __shared__ int64_t lds_n[16 * 6];
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
@@ -52,7 +52,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const 
         acc[4] |= (len < 0 || st < 0 || st + len > src.cap);
         acc[5] |= (kp < 0 || kp > len);
         const int64_t nch = len > 0 ? (len + CMP_CHUNK - 1) / CMP_CHUNK : 0;
-        const int64_t need = (int64_t)kp + reserve;
+        const int64_t need = ((int64_t)kp + reserve + align - 1) / align * align;   // align = 1 unless pages are built
         acc[3] += nch;
         acc[2] += need;
         if (i < g) {
@@ -191,19 +191,30 @@ __global__ __launch_bounds__(CMP_THREADS) void k_cmp_copy(CacheView src, const u
     }
 }
 
-void launch_cmp_scan(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const int32_t* kept,
-                     const CacheViewMut& dst, int32_t reserve, hipStream_t st) {
+void launch_cmp_scan_aligned(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const int32_t* kept,
+                             const CacheViewMut& dst, int32_t reserve, int32_t align, hipStream_t st) {
     ProfScope prof(ctx, K_CMP_SCAN, st);
     hipLaunchKernelGGL(k_cmp_scan, dim3(ctx->shape.nseg), dim3(SCAN_THREADS), 0, st, src, keep, kept, dst, reserve,
-                       ctx->shape, ctx->ws);
+                       align, ctx->shape, ctx->ws);
+}
+
+void launch_cmp_scan(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const int32_t* kept,
+                     const CacheViewMut& dst, int32_t reserve, hipStream_t st) {
+    launch_cmp_scan_aligned(ctx, src, keep, kept, dst, reserve, 1, st);
 }
 
 kvtrim_status launch_compact(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const int32_t* kept,
                              const CacheViewMut& dst, int32_t reserve, hipStream_t st) {
+    launch_cmp_scan(ctx, src, keep, kept, dst, reserve, st);
+    return launch_cmp_copy(ctx, src, keep, dst, st);
+}
+
+// The row mover alone (the tables of k_cmp_scan must be in the workspace).
+kvtrim_status launch_cmp_copy(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const CacheViewMut& dst,
+                              hipStream_t st) {
     const Shape& sh = ctx->shape;
     const Workspace& ws = ctx->ws;
     const int64_t max_chunks = src.cap / CMP_CHUNK + sh.nseg;
-    launch_cmp_scan(ctx, src, keep, kept, dst, reserve, st);
     if (max_chunks > 0) {
         ProfScope prof(ctx, K_CMP_COPY, st);
         const dim3 grid((unsigned)max_chunks), block(CMP_THREADS);

@@ -1,0 +1,698 @@
+// Paged variant (the layout of Sec. 4.2 "Implementation details"): fixed-size pages, a block
+// table per (sequence, layer, KV head) segment, eviction that frees slots and moves no K/V.
+//
+// The selection and the attention reuse the kernels of the ragged path: a page is a chunk of
+// KVTRIM_PAGE_SIZE slots whose descriptor {first slot, size, segment} comes from the block tables,
+// and a slot takes part only if its position is not negative.  This file holds what is specific
+// to pages: building them from a ragged cache, appending into free slots, the chunk tables, the
+// tie rule by position (a segment's slots are in no particular order), eviction and the
+// bookkeeping of free pages.
+#include "kvtrim_device.h"
+
+namespace kvtrim {
+
+constexpr int P = KVTRIM_PAGE_SIZE;
+
+struct PagedView {
+    uint16_t* k;
+    uint16_t* v;
+    float* log_beta;
+    int32_t* pos;
+    float* log_tail;
+    int32_t* block_table;
+    int32_t* seg_pages;
+    int32_t* seg_live;
+    int32_t* page_owner;
+    int32_t* page_live;
+    int32_t* free_list;
+    int32_t* n_free;
+    int32_t n_pages;
+    int32_t max_pps;
+};
+
+// ---------------------------------------------------------------------------------------------
+// Build: the page-aligned compaction has written the survivors of segment g to the slots
+// [seg_start[g], seg_start[g] + seg_len[g]) with seg_start a multiple of the page size.  Blocks
+// [0, nseg) set up the segment's pages, the remaining blocks the free pages.
+__global__ __launch_bounds__(256) void k_pg_init(PagedView pc, Shape sh, Workspace ws) {
+    if (__hip_atomic_load(ws.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
+    const int tid = threadIdx.x;
+    const int last = sh.nseg - 1;
+    const int used = (int)((ws.pg_seg_start[last] + ((int64_t)ws.pg_seg_len[last] + P - 1) / P * P) / P);
+    if ((int)blockIdx.x < sh.nseg) {
+        const int g = blockIdx.x;
+        const int len = ws.pg_seg_len[g];
+        const int first = (int)(ws.pg_seg_start[g] / P);
+        const int npg = (len + P - 1) / P;
+        if (npg > pc.max_pps || first + npg > pc.n_pages) {          // uniform over the block
+            if (tid == 0) {
+                atomicOr(ws.err, ERR_CAP);
+                pc.seg_pages[g] = 0;
+                pc.seg_live[g] = 0;
+            }
+            return;
+        }
+        for (int i = tid; i < npg; i += 256) {
+            pc.block_table[(int64_t)g * pc.max_pps + i] = first + i;
+            pc.page_owner[first + i] = g;
+            pc.page_live[first + i] = min(P, len - i * P);
+        }
+        if (npg > 0)                                                 // empty tail of the last page
+            for (int j = len - (npg - 1) * P + tid; j < P; j += 256) pc.pos[(int64_t)(first + npg - 1) * P + j] = -1;
+        if (tid == 0) {
+            pc.seg_pages[g] = npg;
+            pc.seg_live[g] = len;
+        }
+        return;
+    }
+    const int nfree = pc.n_pages - used;
+    const int fb = blockIdx.x - sh.nseg, nfb = gridDim.x - sh.nseg;
+    if (fb == 0 && tid == 0) *pc.n_free = nfree;
+    for (int i = fb; i < nfree; i += nfb) {                          // page used + i; popped in ascending order
+        const int page = used + i;
+        if (tid == 0) {
+            pc.page_owner[page] = -1;
+            pc.page_live[page] = 0;
+            pc.free_list[nfree - 1 - i] = page;
+        }
+        if (tid < P) pc.pos[(int64_t)page * P + tid] = -1;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Append: one wavefront per segment.
+__global__ __launch_bounds__(256) void k_pg_append(PagedView pc, const uint16_t* __restrict__ k_new,
+                                                   const uint16_t* __restrict__ v_new,
+                                                   const float* __restrict__ lb_new, const float* __restrict__ lt_new,
+                                                   const int32_t* __restrict__ pos_new, int nseg, int head_dim,
+                                                   int32_t* err) {
+    const int lane = lane_id();
+    const int g = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (g >= nseg) return;                                           // uniform over the wavefront
+    const int npg = pc.seg_pages[g];
+    if (npg < 0 || npg > pc.max_pps) {
+        if (lane == 0) atomicOr(err, ERR_LAYOUT);
+        return;
+    }
+    const int32_t* bt = pc.block_table + (int64_t)g * pc.max_pps;
+    int found = -1;
+    for (int base = 0; base < npg && found < 0; base += 64) {
+        const int i = base + lane;
+        bool ok = false;
+        if (i < npg) {
+            const int pg = bt[i];
+            ok = pg >= 0 && pg < pc.n_pages && pc.page_live[pg] < P;
+        }
+        const uint64_t m = __ballot(ok);
+        if (m) found = base + __ffsll((long long)m) - 1;
+    }
+    int page = -1, slot = 0;
+    if (found >= 0) {
+        page = bt[found];
+        const uint64_t m0 = __ballot(pc.pos[(int64_t)page * P + lane] < 0);
+        const uint64_t m1 = __ballot(pc.pos[(int64_t)page * P + 64 + lane] < 0);
+        if (m0) slot = __ffsll((long long)m0) - 1;
+        else if (m1) slot = 64 + __ffsll((long long)m1) - 1;
+        else {
+            if (lane == 0) atomicOr(err, ERR_LAYOUT);                // page_live disagrees with the slots
+            return;
+        }
+    } else {
+        if (npg >= pc.max_pps) {
+            if (lane == 0) atomicOr(err, ERR_CAP);
+            return;
+        }
+        int got = -1;
+        if (lane == 0) {
+            const int idx = atomicSub(pc.n_free, 1) - 1;
+            if (idx < 0) {
+                atomicAdd(pc.n_free, 1);
+                atomicOr(err, ERR_CAP);
+            } else {
+                got = pc.free_list[idx];
+                if (got < 0 || got >= pc.n_pages) {
+                    atomicOr(err, ERR_LAYOUT);
+                    got = -1;
+                }
+            }
+        }
+        page = __shfl(got, 0, 64);
+        if (page < 0) return;
+        if (lane == 0) {
+            pc.block_table[(int64_t)g * pc.max_pps + npg] = page;
+            pc.page_owner[page] = g;
+            pc.seg_pages[g] = npg + 1;
+        }
+        slot = 0;
+    }
+    const int64_t e = (int64_t)page * P + slot;
+    const int vpr = head_dim / 8;
+    const uint4* ks = reinterpret_cast<const uint4*>(k_new) + (int64_t)g * vpr;
+    const uint4* vs = reinterpret_cast<const uint4*>(v_new) + (int64_t)g * vpr;
+    uint4* kd = reinterpret_cast<uint4*>(pc.k) + e * vpr;
+    uint4* vd = reinterpret_cast<uint4*>(pc.v) + e * vpr;
+    for (int i = lane; i < vpr; i += 64) {
+        kd[i] = ks[i];
+        vd[i] = vs[i];
+    }
+    if (lane == 0) {
+        pc.log_beta[e] = lb_new[g];
+        if (pc.log_tail) pc.log_tail[e] = lt_new[g];
+        pc.pos[e] = pos_new[g];
+        pc.page_live[page] += 1;
+        pc.seg_live[g] += 1;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Score: one block per page, one thread per slot.
+__global__ __launch_bounds__(P) void k_pg_score(PagedView pc, const int32_t* __restrict__ now,
+                                                float* __restrict__ score, int segs_per_seq, int nseg) {
+    const int page = blockIdx.x;
+    const int owner = pc.page_owner[page];
+    if (owner < 0 || owner >= nseg) return;
+    const int64_t e = (int64_t)page * P + threadIdx.x;
+    const int ps = pc.pos[e];
+    if (ps < 0) return;
+    const float elapsed = (float)(now[owner / segs_per_seq] + 1 - ps);
+    score[e] = pc.log_tail ? __fmaf_rn(elapsed, pc.log_beta[e], pc.log_tail[e]) : __fmul_rn(elapsed, pc.log_beta[e]);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Chunk table of a paged cache, built by ONE block: one chunk per page of the segments with
+// in_range(g), in segment order.  prefix[g] = first chunk of segment g, prefix[nseg] = number of
+// chunks; entry_prefix (optional) counts the live entries of the segments before g.  Returns the
+// number of chunks; tables that do not fit (page ids, counts) raise ERR_LAYOUT and leave it empty.
+template <typename InRange>
+__device__ __forceinline__ int build_page_table(const PagedView& pc, int nseg, InRange in_range, int32_t* prefix,
+                                                ChunkDesc* desc, int64_t max_chunks, int64_t* entry_prefix,
+                                                int32_t* err) {
+    __shared__ uint64_t s_scan[17];
+    __shared__ int s_bad;
+    __shared__ int s_c0[1024], s_n[1024];
+    const int tid = threadIdx.x;
+    if (tid == 0) s_bad = 0;
+    __syncthreads();
+    uint64_t carry = 0;
+    for (int base = 0; base < nseg; base += blockDim.x) {
+        const int g = base + tid;
+        uint64_t v = 0;
+        if (g < nseg) {
+            const int npg = pc.seg_pages[g], live = pc.seg_live[g];
+            if (npg < 0 || npg > pc.max_pps || live < 0 || (int64_t)live > (int64_t)npg * P) s_bad = 1;
+            else if (in_range(g)) v = ((uint64_t)live << 32) | (uint64_t)npg;
+        }
+        uint64_t tot;
+        const uint64_t ex = carry + block_excl_scan<uint64_t>(v, s_scan, &tot);
+        carry += tot;
+        const int c0 = (int)(ex & 0xffffffffu), n = (int)(v & 0xffffffffu);
+        if (g < nseg) {
+            prefix[g] = c0;
+            if (entry_prefix) entry_prefix[g] = (int64_t)(ex >> 32);
+        }
+        s_c0[tid] = c0;
+        s_n[tid] = n;
+        __syncthreads();
+        const bool fits = !s_bad && (int64_t)(carry & 0xffffffffu) <= max_chunks;
+        if (fits) {                                                  // one wavefront per segment of the tile
+            const int lane = lane_id(), wave = tid >> 6, nw = blockDim.x >> 6;
+            const int ntile = min((int)blockDim.x, nseg - base);
+            for (int t = wave; t < ntile; t += nw) {
+                const int gg = base + t, cc = s_c0[t], nn = s_n[t];
+                const int32_t* bt = pc.block_table + (int64_t)gg * pc.max_pps;
+                for (int i = lane; i < nn; i += 64) {
+                    const int pg = bt[i];
+                    if (pg < 0 || pg >= pc.n_pages) s_bad = 1;
+                    ChunkDesc d;
+                    d.first = (int64_t)max(pg, 0) * P;
+                    d.n = P;
+                    d.seg = gg;
+                    desc[cc + i] = d;
+                }
+            }
+        }
+        __syncthreads();
+    }
+    const int64_t total = (int64_t)(carry & 0xffffffffu);
+    if (s_bad || total > max_chunks) {
+        if (tid == 0) atomicOr(err, ERR_LAYOUT);
+        for (int g = tid; g <= nseg; g += blockDim.x) {
+            prefix[g] = 0;
+            if (entry_prefix) entry_prefix[g] = 0;
+        }
+        __syncthreads();
+        return 0;
+    }
+    if (tid == 0) {
+        prefix[nseg] = (int32_t)total;
+        if (entry_prefix) entry_prefix[nseg] = (int64_t)(carry >> 32);
+    }
+    __syncthreads();
+    return (int)total;
+}
+
+constexpr int PG_PLAN_ZERO_BLOCKS = 8;
+
+// Plan of the paged selection: block 0 builds the chunk table (in the compaction's table slots of
+// the workspace, which a paged step does not otherwise use), the chunk range of every histogram
+// block and the per-sequence state; the other blocks clear the histograms.
+__global__ __launch_bounds__(1024) void k_pg_plan(PagedView pc, Shape sh, const int64_t* __restrict__ budget,
+                                                  Workspace ws, int32_t* __restrict__ kept_out,
+                                                  uint32_t* __restrict__ thr_out, int hist_blocks) {
+    if (blockIdx.x > 0) {
+        const int n = 3 * HIST_REPLICAS * sh.n_seq * RADIX_BINS;
+        for (int i = (blockIdx.x - 1) * blockDim.x + threadIdx.x; i < n; i += (gridDim.x - 1) * blockDim.x)
+            ws.hist[i] = 0;
+        return;
+    }
+    const int tid = threadIdx.x;
+    for (int i = tid; i < DONE_WORDS; i += blockDim.x) ws.done[i] = 0;
+    for (int g = tid; g < sh.nseg; g += blockDim.x) {
+        kept_out[g] = 0;
+        ws.tie_cnt[g] = 0;
+        ws.tie_mode[g] = 0;
+        ws.tie_thr[g] = 0;
+    }
+    const int total = build_page_table(pc, sh.nseg, [](int) { return true; }, ws.cmp_chunk_prefix, ws.cmp_desc,
+                                       ws.max_cmp_chunks, ws.sel_entry_prefix, ws.err);
+    if (tid < hist_blocks) {
+        const int cpb = (total + hist_blocks - 1) / hist_blocks;
+        const int c0 = min(total, tid * cpb), c1 = min(total, c0 + cpb);
+        int4 r = make_int4(c0, c1, 0, -1);
+        if (c0 < c1) {
+            r.z = ws.cmp_desc[c0].seg / sh.segs_per_seq;
+            r.w = ws.cmp_desc[c1 - 1].seg / sh.segs_per_seq;
+        }
+        ws.sel_blk[tid] = r;
+    }
+    for (int seq = tid; seq < sh.n_seq; seq += blockDim.x) {
+        const int64_t n = ws.sel_entry_prefix[(seq + 1) * sh.segs_per_seq] - ws.sel_entry_prefix[seq * sh.segs_per_seq];
+        int64_t b = budget[seq];
+        if (b < 0) b = 0;
+        SelState st;
+        st.prefix = 0;
+        st.thr_key = 0xFFFFFFFFu;
+        st.count = n;
+        st.want = b < n ? b : n;
+        st.rank = st.want;
+        st.tie_quota = 0;
+        st.keep_none = st.want == 0;
+        st.need_rank = 0;
+        ws.sel[seq] = st;
+        if (thr_out) thr_out[seq] = 0xFFFFFFFFu;
+    }
+}
+
+__global__ __launch_bounds__(1024) void k_pg_att_plan(PagedView pc, Shape sh, Workspace ws, int layer_begin,
+                                                      int layer_end) {
+    const int H = sh.n_kv_heads, L = sh.n_layers;
+    auto in_range = [=](int g) {
+        const int layer = (g / H) % L;
+        return layer >= layer_begin && layer < layer_end;
+    };
+    build_page_table(pc, sh.nseg, in_range, ws.att_chunk_prefix, ws.att_desc, ws.max_att_chunks, nullptr, ws.err);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Ties that do not all fit.  Per page of such a sequence: slots above the threshold are credited
+// to the segment, slots equal to it are counted per segment.  The last block to finish turns the
+// quota of every sequence into a rule per segment - in (layer, head) order the ties of a segment
+// all survive, or none does, and in at most one segment only the q ties with the smallest
+// positions survive; that position bound is found by a radix select over the segment's ties.
+constexpr int PGC_THREADS = 1024;
+
+__device__ __forceinline__ bool is_tie(const PagedView& pc, const float* score, int64_t e, uint32_t thr, int* pos_out) {
+    const int ps = pc.pos[e];
+    *pos_out = ps;
+    return ps >= 0 && key_of_score(score[e]) == thr;
+}
+
+__global__ __launch_bounds__(PGC_THREADS) void k_pg_count(PagedView pc, const float* __restrict__ score, Shape sh,
+                                                          Workspace ws, int32_t* __restrict__ kept_out) {
+    __shared__ int64_t lds64[17];
+    __shared__ int32_t lds32[17];
+    __shared__ uint32_t h[2048];
+    __shared__ int is_last, s_part_seg, s_part_q, s_digit, s_rank;
+    if (ws.done[127] == 0) return;                                   // uniform over the grid
+    const int tid = threadIdx.x;
+    const int total = ws.cmp_chunk_prefix[sh.nseg];
+    for (int ch = blockIdx.x; ch < total; ch += gridDim.x) {
+        const ChunkDesc d = ws.cmp_desc[ch];
+        const SelState st = ws.sel[d.seg / sh.segs_per_seq];
+        if (!st.need_rank) continue;                                 // uniform over the block
+        int gt = 0, eq = 0;
+        if (tid < P) {
+            const int64_t e = d.first + tid;
+            if (pc.pos[e] >= 0) {
+                const uint32_t key = key_of_score(score[e]);
+                gt = key > st.thr_key;
+                eq = key == st.thr_key;
+            }
+        }
+        gt = block_sum<int32_t>(gt, lds32);
+        eq = block_sum<int32_t>(eq, lds32);
+        if (tid == 0) {
+            if (gt) atomicAdd(&kept_out[d.seg], gt);
+            if (eq) atomicAdd(&ws.tie_cnt[d.seg], eq);
+        }
+    }
+    __syncthreads();
+    if (tid == 0) is_last = arrive_last(ws.done + 32 * 3);
+    __syncthreads();
+    if (!is_last) return;
+    __threadfence();
+
+    for (int seq = 0; seq < sh.n_seq; ++seq) {
+        const SelState st = ws.sel[seq];
+        if (!st.need_rank) continue;
+        if (tid == 0) s_part_seg = -1;
+        __syncthreads();
+        int64_t running = 0;
+        for (int base = 0; base < sh.segs_per_seq; base += PGC_THREADS) {
+            const int i = base + tid;
+            const int g = seq * sh.segs_per_seq + i;
+            const int64_t v = i < sh.segs_per_seq
+                                  ? (int64_t)__hip_atomic_load(&ws.tie_cnt[g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+            int64_t tot;
+            const int64_t ex = block_excl_scan<int64_t>(v, lds64, &tot);
+            if (i < sh.segs_per_seq && v > 0) {
+                const int64_t before = running + ex;
+                if (before + v <= st.tie_quota) {
+                    ws.tie_mode[g] = 1;
+                    atomicAdd(&kept_out[g], (int32_t)v);
+                } else if (before < st.tie_quota) {
+                    s_part_seg = g;
+                    s_part_q = (int)(st.tie_quota - before);
+                }                                                    // else mode 0 (set by the plan)
+            }
+            running += tot;
+        }
+        __syncthreads();
+        const int g = s_part_seg;
+        if (g < 0) continue;                                         // uniform over the block
+        // the q-th smallest position among the ties of segment g: 11 + 10 + 10 bits, most significant first
+        const int npg = pc.seg_pages[g];
+        const int32_t* bt = pc.block_table + (int64_t)g * pc.max_pps;
+        if (tid == 0) s_rank = s_part_q;
+        uint32_t prefix = 0;
+        for (int pass = 0; pass < 3; ++pass) {
+            const int shift = pass == 0 ? 20 : (pass == 1 ? 10 : 0);
+            const int nb = pass == 0 ? 2048 : 1024;
+            for (int i = tid; i < 2048; i += PGC_THREADS) h[i] = 0;
+            __syncthreads();
+            for (int64_t s = tid; s < (int64_t)npg * P; s += PGC_THREADS) {
+                const int64_t e = (int64_t)bt[s / P] * P + (s % P);
+                int ps;
+                if (is_tie(pc, score, e, st.thr_key, &ps)) {
+                    const uint32_t up = (uint32_t)ps;
+                    const bool match = pass == 0 ? true : (pass == 1 ? (up >> 20) == prefix : (up >> 10) == prefix);
+                    if (match) atomicAdd(&h[(up >> shift) & (nb - 1)], 1u);
+                }
+            }
+            __syncthreads();
+            // ascending walk: thread t owns bins 2t, 2t+1
+            const uint32_t c0 = h[2 * tid], c1 = h[2 * tid + 1];
+            int32_t tot;
+            const int32_t below = block_excl_scan<int32_t>((int32_t)(c0 + c1), lds32, &tot);
+            const int rank = s_rank;
+            __syncthreads();
+            if (below < rank && rank <= below + (int32_t)(c0 + c1)) {
+                if (rank <= below + (int32_t)c0) {
+                    s_digit = 2 * tid;
+                    s_rank = rank - below;
+                } else {
+                    s_digit = 2 * tid + 1;
+                    s_rank = rank - below - (int32_t)c0;
+                }
+            }
+            __syncthreads();
+            prefix = (prefix << (pass == 0 ? 11 : 10)) | (uint32_t)s_digit;
+        }
+        if (tid == 0) {
+            ws.tie_mode[g] = 2;
+            ws.tie_thr[g] = (int32_t)prefix;
+            atomicAdd(&kept_out[g], s_part_q);
+        }
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Eviction: one block per page.  A page left without a live entry is marked for release
+// (owner -2); k_pg_tidy takes it out of its segment's block table and pushes it on the free list.
+__global__ __launch_bounds__(P) void k_pg_evict(PagedView pc, const uint8_t* __restrict__ keep, int nseg) {
+    __shared__ int s_cnt[P / 64];
+    const int page = blockIdx.x;
+    const int owner = pc.page_owner[page];
+    if (owner < 0 || owner >= nseg) return;                          // uniform over the block
+    const int64_t e = (int64_t)page * P + threadIdx.x;
+    const bool ev = pc.pos[e] >= 0 && keep[e] == 0;
+    if (ev) pc.pos[e] = -1;
+    const int c = __popcll(__ballot(ev));
+    if (lane_id() == 0) s_cnt[threadIdx.x >> 6] = c;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int n = 0;
+        for (int w = 0; w < P / 64; ++w) n += s_cnt[w];
+        if (n) {
+            const int left = pc.page_live[page] - n;
+            pc.page_live[page] = left;
+            atomicSub(&pc.seg_live[owner], n);
+            if (left <= 0) pc.page_owner[page] = -2;
+        }
+    }
+}
+
+// One block per segment: drops the pages marked for release from the block table (order of the
+// others kept) and returns them to the free list.
+__global__ __launch_bounds__(256) void k_pg_tidy(PagedView pc, int32_t* err) {
+    __shared__ int32_t lds32[17];
+    __shared__ int32_t s_page[256];
+    const int g = blockIdx.x, tid = threadIdx.x;
+    const int npg = pc.seg_pages[g];
+    if (npg < 0 || npg > pc.max_pps) {
+        if (tid == 0) atomicOr(err, ERR_LAYOUT);
+        return;
+    }
+    int32_t* bt = pc.block_table + (int64_t)g * pc.max_pps;
+    int out = 0;
+    for (int base = 0; base < npg; base += 256) {                    // read a tile, then write it: out <= base
+        const int i = base + tid;
+        int page = -1;
+        bool alive = false;
+        if (i < npg) {
+            page = bt[i];
+            if (page >= 0 && page < pc.n_pages) {
+                alive = pc.page_owner[page] == g;
+                if (!alive && pc.page_owner[page] == -2) {          // release
+                    pc.page_owner[page] = -1;
+                    pc.page_live[page] = 0;
+                    const int idx = atomicAdd(pc.n_free, 1);
+                    if (idx >= 0 && idx < pc.n_pages) pc.free_list[idx] = page;
+                }
+            }
+        }
+        int32_t tot;
+        const int32_t ex = block_excl_scan<int32_t>(alive ? 1 : 0, lds32, &tot);
+        s_page[tid] = page;
+        __syncthreads();
+        if (alive) bt[out + ex] = s_page[tid];
+        __syncthreads();
+        out += tot;
+    }
+    if (tid == 0) pc.seg_pages[g] = out;
+}
+
+// ---------------------------------------------------------------------------------------------
+static PagedView view_of(const kvtrim_paged_cache* c) {
+    PagedView v;
+    v.k = (uint16_t*)c->k;
+    v.v = (uint16_t*)c->v;
+    v.log_beta = c->log_beta;
+    v.pos = c->pos;
+    v.log_tail = c->log_tail;
+    v.block_table = c->block_table;
+    v.seg_pages = c->seg_pages;
+    v.seg_live = c->seg_live;
+    v.page_owner = c->page_owner;
+    v.page_live = c->page_live;
+    v.free_list = c->free_list;
+    v.n_free = c->n_free;
+    v.n_pages = c->n_pages;
+    v.max_pps = c->max_pages_per_seg;
+    return v;
+}
+
+static CacheView pool_view(const kvtrim_paged_cache* c) {
+    CacheView v;
+    v.k = (const uint16_t*)c->k;
+    v.v = (const uint16_t*)c->v;
+    v.log_beta = c->log_beta;
+    v.pos = c->pos;
+    v.seg_start = nullptr;
+    v.seg_len = nullptr;
+    v.cap = (int64_t)c->n_pages * P;
+    v.log_tail = c->log_tail;
+    return v;
+}
+
+static const char* paged_problem(const kvtrim_ctx* ctx, const kvtrim_paged_cache* c) {
+    if (!c) return "paged cache is NULL";
+    if (!c->k || !c->v || !c->log_beta || !c->pos || !c->block_table || !c->seg_pages || !c->seg_live ||
+        !c->page_owner || !c->page_live || !c->free_list || !c->n_free)
+        return "paged cache has a NULL pointer";
+    if ((((uintptr_t)c->k) | ((uintptr_t)c->v)) & 15) return "k/v not 16-byte aligned";
+    if (c->n_pages < 1 || c->max_pages_per_seg < 1) return "n_pages / max_pages_per_seg < 1";
+    if ((int64_t)c->n_pages * P > ctx->cfg.max_entries) return "n_pages * page size exceeds max_entries";
+    return nullptr;
+}
+
+static kvtrim_status bad(kvtrim_ctx* ctx, const char* why) {
+    snprintf(ctx->last_error, sizeof(ctx->last_error), "invalid argument: %s", why);
+    return KVTRIM_EINVAL;
+}
+
+}  // namespace kvtrim
+
+using namespace kvtrim;
+
+extern "C" {
+
+kvtrim_status kvtrim_paged_build(kvtrim_ctx* ctx, const kvtrim_cache* src, const uint8_t* keep, const int32_t* kept,
+                                 kvtrim_paged_cache* dst, void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    if (const char* p = paged_problem(ctx, dst)) return bad(ctx, p);
+    if (!src || !src->k || !src->v || !src->log_beta || !src->pos || !src->seg_start || !src->seg_len || !keep || !kept)
+        return bad(ctx, "src / keep / kept has a NULL pointer");
+    if (src->cap_entries < 1 || src->cap_entries > ctx->cfg.max_entries) return bad(ctx, "src cap_entries outside [1, max_entries]");
+    if ((src->log_tail == nullptr) != (dst->log_tail == nullptr)) return bad(ctx, "log_tail must be set in both caches or in neither");
+    if (src->k == dst->k || src->v == dst->v || src->log_beta == dst->log_beta || src->pos == dst->pos)
+        return bad(ctx, "src and dst share a buffer");
+    hipStream_t st = (hipStream_t)hip_stream;
+    CacheView sv;
+    sv.k = (const uint16_t*)src->k;
+    sv.v = (const uint16_t*)src->v;
+    sv.log_beta = src->log_beta;
+    sv.pos = src->pos;
+    sv.seg_start = src->seg_start;
+    sv.seg_len = src->seg_len;
+    sv.cap = src->cap_entries;
+    sv.log_tail = src->log_tail;
+    CacheViewMut dv;
+    dv.k = (uint16_t*)dst->k;
+    dv.v = (uint16_t*)dst->v;
+    dv.log_beta = dst->log_beta;
+    dv.pos = dst->pos;
+    dv.seg_start = ctx->ws.pg_seg_start;
+    dv.seg_len = ctx->ws.pg_seg_len;
+    dv.cap = (int64_t)dst->n_pages * P;
+    dv.log_tail = dst->log_tail;
+    launch_cmp_scan_aligned(ctx, sv, keep, kept, dv, 0, P, st);
+    kvtrim_status rc = launch_cmp_copy(ctx, sv, keep, dv, st);
+    if (rc != KVTRIM_OK) return rc;
+    {
+        ProfScope prof(ctx, K_PG_INIT, st);
+        const int free_blocks = dst->n_pages < 1024 ? dst->n_pages : 1024;
+        hipLaunchKernelGGL(k_pg_init, dim3(ctx->shape.nseg + free_blocks), dim3(256), 0, st, view_of(dst), ctx->shape, ctx->ws);
+    }
+    KVTRIM_HIP(ctx, hipGetLastError());
+    return KVTRIM_OK;
+}
+
+kvtrim_status kvtrim_paged_append(kvtrim_ctx* ctx, kvtrim_paged_cache* c, const void* k_new, const void* v_new,
+                                  const float* log_beta_new, const float* log_tail_new, const int32_t* pos_new,
+                                  void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    if (const char* p = paged_problem(ctx, c)) return bad(ctx, p);
+    if (!k_new || !v_new || !log_beta_new || !pos_new) return bad(ctx, "a new-token pointer is NULL");
+    if ((((uintptr_t)k_new) | ((uintptr_t)v_new)) & 15) return bad(ctx, "k_new / v_new not 16-byte aligned");
+    if ((c->log_tail == nullptr) != (log_tail_new == nullptr))
+        return bad(ctx, "log_tail_new is required exactly when the cache carries log_tail");
+    hipStream_t st = (hipStream_t)hip_stream;
+    ProfScope prof(ctx, K_PG_APPEND, st);
+    hipLaunchKernelGGL(k_pg_append, dim3((ctx->shape.nseg + 3) / 4), dim3(256), 0, st, view_of(c), (const uint16_t*)k_new,
+                       (const uint16_t*)v_new, log_beta_new, log_tail_new, pos_new, ctx->shape.nseg, ctx->shape.head_dim,
+                       ctx->ws.err);
+    KVTRIM_HIP(ctx, hipGetLastError());
+    return KVTRIM_OK;
+}
+
+kvtrim_status kvtrim_paged_score(kvtrim_ctx* ctx, const kvtrim_paged_cache* c, const int32_t* now, float* score_out,
+                                 void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    if (const char* p = paged_problem(ctx, c)) return bad(ctx, p);
+    if (!now || !score_out) return bad(ctx, "now / score_out is NULL");
+    hipStream_t st = (hipStream_t)hip_stream;
+    ProfScope prof(ctx, K_PG_SCORE, st);
+    hipLaunchKernelGGL(k_pg_score, dim3(c->n_pages), dim3(P), 0, st, view_of(c), now, score_out, ctx->shape.segs_per_seq,
+                       ctx->shape.nseg);
+    KVTRIM_HIP(ctx, hipGetLastError());
+    return KVTRIM_OK;
+}
+
+kvtrim_status kvtrim_paged_select(kvtrim_ctx* ctx, const kvtrim_paged_cache* c, const float* score, const int64_t* budget,
+                                  uint8_t* keep_out, int32_t* kept_out, uint32_t* thr_key_out, void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    if (const char* p = paged_problem(ctx, c)) return bad(ctx, p);
+    if (!score || !budget || !keep_out || !kept_out) return bad(ctx, "score / budget / keep_out / kept_out is NULL");
+    hipStream_t st = (hipStream_t)hip_stream;
+    const PagedView pv = view_of(c);
+    const int hist_blocks = c->n_pages < HIST_BLOCKS_MAX ? c->n_pages : HIST_BLOCKS_MAX;
+    {
+        ProfScope prof(ctx, K_PG_PLAN, st);
+        hipLaunchKernelGGL(k_pg_plan, dim3(1 + PG_PLAN_ZERO_BLOCKS), dim3(1024), 0, st, pv, ctx->shape, budget, ctx->ws,
+                           kept_out, thr_key_out, hist_blocks);
+    }
+    SelTables tb;
+    tb.desc = ctx->ws.cmp_desc;
+    tb.prefix = ctx->ws.cmp_chunk_prefix;
+    tb.pos = c->pos;
+    for (int pass = 0; pass < 3; ++pass) launch_select_passes_paged(ctx, score, tb, hist_blocks, pass, thr_key_out, st);
+    {
+        ProfScope prof(ctx, K_PG_COUNT, st);
+        hipLaunchKernelGGL(k_pg_count, dim3(c->n_pages < 256 ? c->n_pages : 256), dim3(PGC_THREADS), 0, st, pv, score,
+                           ctx->shape, ctx->ws, kept_out);
+    }
+    launch_select_mask_paged(ctx, score, tb, c->n_pages, keep_out, kept_out, st);
+    KVTRIM_HIP(ctx, hipGetLastError());
+    return KVTRIM_OK;
+}
+
+kvtrim_status kvtrim_paged_evict(kvtrim_ctx* ctx, kvtrim_paged_cache* c, const uint8_t* keep, void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    if (const char* p = paged_problem(ctx, c)) return bad(ctx, p);
+    if (!keep) return bad(ctx, "keep is NULL");
+    hipStream_t st = (hipStream_t)hip_stream;
+    const PagedView pv = view_of(c);
+    {
+        ProfScope prof(ctx, K_PG_EVICT, st);
+        hipLaunchKernelGGL(k_pg_evict, dim3(c->n_pages), dim3(P), 0, st, pv, keep, ctx->shape.nseg);
+    }
+    {
+        ProfScope prof(ctx, K_PG_TIDY, st);
+        hipLaunchKernelGGL(k_pg_tidy, dim3(ctx->shape.nseg), dim3(256), 0, st, pv, ctx->ws.err);
+    }
+    KVTRIM_HIP(ctx, hipGetLastError());
+    return KVTRIM_OK;
+}
+
+kvtrim_status kvtrim_paged_attn(kvtrim_ctx* ctx, const kvtrim_paged_cache* c, const void* q, int32_t layer_begin,
+                                int32_t layer_end, float softmax_scale, float* out, float* lse, void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    if (const char* p = paged_problem(ctx, c)) return bad(ctx, p);
+    if (!q || !out) return bad(ctx, "q / out is NULL");
+    if (((uintptr_t)q) & 15) return bad(ctx, "q not 16-byte aligned");
+    if (layer_begin < 0 || layer_end > ctx->cfg.n_layers || layer_begin >= layer_end)
+        return bad(ctx, "empty or out-of-range layer range");
+    if (!(softmax_scale == softmax_scale)) return bad(ctx, "softmax_scale is NaN");
+    if (c->n_pages > ctx->ws.max_att_chunks) return bad(ctx, "too many pages for the partial-result buffer of this context");
+    hipStream_t st = (hipStream_t)hip_stream;
+    {
+        ProfScope prof(ctx, K_PG_ATT_PLAN, st);
+        hipLaunchKernelGGL(k_pg_att_plan, dim3(1), dim3(1024), 0, st, view_of(c), ctx->shape, ctx->ws, layer_begin, layer_end);
+    }
+    return launch_attn_paged(ctx, pool_view(c), (const uint16_t*)q, c->n_pages, layer_begin, layer_end, softmax_scale, out,
+                             lse, st);
+}
+
+}  // extern "C"

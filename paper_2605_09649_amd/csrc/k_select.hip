@@ -59,28 +59,17 @@ __global__ __launch_bounds__(1024) void k_sel_plan(CacheView c, Shape sh, const 
     }
 }
 
-// "Last block done" detection, called by one thread per block after the block's results are
-// written.  Device-scope atomics on ONE address are served one after the other (tens of
-// nanoseconds each), so 256 blocks do not meet on one counter: 16 group counters first, then the
-// last block of each group on the top-level counter.  counters: [0] top level, [1..16] groups.
-__device__ __forceinline__ bool arrive_last(uint32_t* counters) {
-    __threadfence();
-    const unsigned grp = blockIdx.x & 15u;
-    const unsigned gsize = (gridDim.x - grp + 15u) / 16u;        // blocks with this group number
-    if (atomicAdd(&counters[1 + grp], 1u) != gsize - 1) return false;
-    __threadfence();
-    const unsigned ngroups = gridDim.x < 16u ? gridDim.x : 16u;
-    return atomicAdd(&counters[0], 1u) == ngroups - 1;
-}
-
 // Histogram of the next digit over the entries whose higher digits equal the prefix found so
 // far.  A block takes a contiguous range of chunks and walks it as a flat range of entry slots
 // (every load independent of the previous one); its LDS histogram is flushed per sequence.
 // Only one thread per block issues the device-scope fence (a fence per wavefront costs an L2
 // write-back each and dominated the pass).
-template <int PASS>
+// SHIFT = log2 of the chunk size of the table (2048-entry chunks of a ragged cache, 128-slot pages of a
+// paged one); PAGED: a slot counts only if its position is not negative.
+template <int PASS, int SHIFT, bool PAGED>
 __global__ __launch_bounds__(HIST_THREADS) void k_sel_hist(const float* __restrict__ score, Shape sh,
-                                                           Workspace ws, uint32_t* __restrict__ thr_out) {
+                                                           Workspace ws, SelTables tb,
+                                                           uint32_t* __restrict__ thr_out) {
     constexpr int NB = PASS == 2 ? 1024 : 2048;
     constexpr int HIST_TILE = 64;
     __shared__ uint32_t h[NB];
@@ -97,8 +86,8 @@ __global__ __launch_bounds__(HIST_THREADS) void k_sel_hist(const float* __restri
         for (int i = tid; i < NB; i += HIST_THREADS) h[i] = 0;
         const int seq_lo = rng.z, seq_hi = rng.w;
         for (int seq = seq_lo; seq <= seq_hi; ++seq) {
-            const int a = max(c0, ws.sel_chunk_prefix[seq * sh.segs_per_seq]);
-            const int b = min(c1, ws.sel_chunk_prefix[(seq + 1) * sh.segs_per_seq]);
+            const int a = max(c0, tb.prefix[seq * sh.segs_per_seq]);
+            const int b = min(c1, tb.prefix[(seq + 1) * sh.segs_per_seq]);
             if (a >= b) continue;
             const uint32_t prefix = ws.sel[seq].prefix;
             if (ws.sel[seq].keep_none) continue;
@@ -107,13 +96,13 @@ __global__ __launch_bounds__(HIST_THREADS) void k_sel_hist(const float* __restri
             for (int t0 = a; t0 < b; t0 += HIST_TILE) {
                 const int nt = min(HIST_TILE, b - t0);
                 __syncthreads();
-                if (tid < nt) s_desc[tid] = ws.sel_desc[t0 + tid];
+                if (tid < nt) s_desc[tid] = tb.desc[t0 + tid];
                 __syncthreads();
 #pragma unroll 8
-                for (int slot = tid; slot < (nt << SEL_SHIFT); slot += HIST_THREADS) {
-                    const ChunkDesc d = s_desc[slot >> SEL_SHIFT];
-                    const int j = slot & (SEL_CHUNK - 1);
-                    if (j < d.n) {
+                for (int slot = tid; slot < (nt << SHIFT); slot += HIST_THREADS) {
+                    const ChunkDesc d = s_desc[slot >> SHIFT];
+                    const int j = slot & ((1 << SHIFT) - 1);
+                    if (j < d.n && (!PAGED || tb.pos[d.first + j] >= 0)) {
                         int bin;
                         if (digit_of<PASS>(key_of_score(score[d.first + j]), prefix, &bin)) atomicAdd(&h[bin], 1u);
                     }
@@ -188,15 +177,16 @@ __global__ __launch_bounds__(HIST_THREADS) void k_sel_hist(const float* __restri
 // equal to it; the last block then turns the per-chunk tie counts into exclusive prefixes per
 // sequence and credits the ties that fit into the quota to their segments.
 __global__ __launch_bounds__(CNT_THREADS) void k_sel_count(const float* __restrict__ score, Shape sh,
-                                                           Workspace ws, int32_t* __restrict__ kept_out) {
+                                                           Workspace ws, SelTables tb,
+                                                           int32_t* __restrict__ kept_out) {
     __shared__ int64_t lds64[17];
     __shared__ int32_t lds32[17];
     __shared__ int is_last;
     if (ws.done[127] == 0) return;                                // uniform over the grid
     const int tid = threadIdx.x;
-    const int total = ws.sel_chunk_prefix[sh.nseg];
+    const int total = tb.prefix[sh.nseg];
     for (int ch = blockIdx.x; ch < total; ch += gridDim.x) {
-        const ChunkDesc d = ws.sel_desc[ch];
+        const ChunkDesc d = tb.desc[ch];
         const SelState st = ws.sel[d.seg / sh.segs_per_seq];
         if (st.need_rank) {                                       // uniform over the block
             int gt = 0, eq = 0;
@@ -221,8 +211,8 @@ __global__ __launch_bounds__(CNT_THREADS) void k_sel_count(const float* __restri
 
     for (int seq = 0; seq < sh.n_seq; ++seq) {
         if (!ws.sel[seq].need_rank) continue;
-        const int cb = ws.sel_chunk_prefix[seq * sh.segs_per_seq];
-        const int ce = ws.sel_chunk_prefix[(seq + 1) * sh.segs_per_seq];
+        const int cb = tb.prefix[seq * sh.segs_per_seq];
+        const int ce = tb.prefix[(seq + 1) * sh.segs_per_seq];
         const int64_t quota = ws.sel[seq].tie_quota;
         int64_t running = 0;
         for (int base = cb; base < ce; base += CNT_THREADS) {
@@ -231,11 +221,11 @@ __global__ __launch_bounds__(CNT_THREADS) void k_sel_count(const float* __restri
             int64_t tot;
             int64_t ex = block_excl_scan<int64_t>(v, lds64, &tot);
             if (cc < ce) {
-                const int64_t tb = running + ex;
-                ws.chunk_tie_base[cc] = tb;
-                if (v > 0 && tb < quota) {
-                    const int64_t take = min(v, quota - tb);
-                    atomicAdd(&kept_out[ws.sel_desc[cc].seg], (int32_t)take);
+                const int64_t tbase = running + ex;
+                ws.chunk_tie_base[cc] = tbase;
+                if (v > 0 && tbase < quota) {
+                    const int64_t take = min(v, quota - tbase);
+                    atomicAdd(&kept_out[tb.desc[cc].seg], (int32_t)take);
                 }
             }
             running += tot;
@@ -244,20 +234,25 @@ __global__ __launch_bounds__(CNT_THREADS) void k_sel_count(const float* __restri
 }
 
 // keep[e] = key > thr, or key == thr and the entry is among the first `quota` ties of its
-// sequence in storage order.  When every tie fits (the usual case) the kernel also counts the
-// survivors of its chunk into kept_out; otherwise k_sel_count has done that.
+// sequence in (segment, position) order.  When every tie fits (the usual case) the kernel also
+// counts the survivors of its chunk into kept_out; otherwise the count kernel has done that.
+// Ragged caches store a segment in position order, so the ties are ranked by storage order
+// (exclusive tie counts per chunk); a paged cache stores them in any order, so the count kernel
+// has turned the quota into a rule per segment: all ties, none, or those up to a position.
+template <int SHIFT, bool PAGED>
 __global__ __launch_bounds__(SEL_THREADS) void k_sel_mask(const float* __restrict__ score, Shape sh,
-                                                          Workspace ws, uint8_t* __restrict__ keep,
+                                                          Workspace ws, SelTables tb, uint8_t* __restrict__ keep,
                                                           int32_t* __restrict__ kept_out) {
     __shared__ int32_t lds32[17];
     const int tid = threadIdx.x;
-    const int total = ws.sel_chunk_prefix[sh.nseg];
+    const int total = tb.prefix[sh.nseg];
     const int ch = blockIdx.x;
     if (ch >= total) return;
-    const ChunkDesc d = ws.sel_desc[ch];
+    const ChunkDesc d = tb.desc[ch];
     const SelState st = ws.sel[d.seg / sh.segs_per_seq];
     const float* s = score + d.first;
     uint8_t* kp = keep + d.first;
+    const int32_t* ps = PAGED ? tb.pos + d.first : nullptr;
     if (st.keep_none) {
         for (int j = tid; j < d.n; j += SEL_THREADS) kp[j] = 0;
         return;
@@ -266,7 +261,7 @@ __global__ __launch_bounds__(SEL_THREADS) void k_sel_mask(const float* __restric
         int n = 0;
 #pragma unroll 8
         for (int j = tid; j < d.n; j += SEL_THREADS) {
-            const bool k = key_of_score(s[j]) >= st.thr_key;
+            const bool k = key_of_score(s[j]) >= st.thr_key && (!PAGED || ps[j] >= 0);
             kp[j] = k;
             n += k;
         }
@@ -274,18 +269,28 @@ __global__ __launch_bounds__(SEL_THREADS) void k_sel_mask(const float* __restric
         if (tid == 0 && n) atomicAdd(&kept_out[d.seg], n);
         return;
     }
-    const int64_t tb = ws.chunk_tie_base[ch];
+    if (PAGED) {
+        const int mode = ws.tie_mode[d.seg];                      // 0: no tie survives, 1: all, 2: positions <= tie_thr
+        const int pthr = ws.tie_thr[d.seg];
+        for (int j = tid; j < d.n; j += SEL_THREADS) {
+            const uint32_t key = key_of_score(s[j]);
+            const int p = ps[j];
+            kp[j] = p >= 0 && (key > st.thr_key || (key == st.thr_key && (mode == 1 || (mode == 2 && p <= pthr))));
+        }
+        return;
+    }
+    const int64_t tbase = ws.chunk_tie_base[ch];
     const int eq_total = ws.chunk_eq[ch];
-    if (eq_total == 0 || tb + eq_total <= st.tie_quota) {        // every tie of this chunk survives
+    if (eq_total == 0 || tbase + eq_total <= st.tie_quota) {     // every tie of this chunk survives
         for (int j = tid; j < d.n; j += SEL_THREADS) kp[j] = key_of_score(s[j]) >= st.thr_key;
         return;
     }
-    if (tb >= st.tie_quota) {                                     // no tie of this chunk survives
+    if (tbase >= st.tie_quota) {                                  // no tie of this chunk survives
         for (int j = tid; j < d.n; j += SEL_THREADS) kp[j] = key_of_score(s[j]) > st.thr_key;
         return;
     }
     // the quota runs out inside this chunk: rank the ties in order
-    int64_t running = tb;
+    int64_t running = tbase;
     for (int base = 0; base < d.n; base += SEL_THREADS) {         // uniform trip count
         const int j = base + tid;
         uint32_t key = 0;
@@ -301,6 +306,31 @@ __global__ __launch_bounds__(SEL_THREADS) void k_sel_mask(const float* __restric
     }
 }
 
+// The three histogram passes and the mask over a paged cache whose chunk table (one chunk per
+// page) is in tb; the plan and the tie count of the paged layout live in k_paged.hip.
+void launch_select_passes_paged(kvtrim_ctx* ctx, const float* score, const SelTables& tb, int hist_blocks,
+                                int pass, uint32_t* thr, hipStream_t st) {
+    const Shape& sh = ctx->shape;
+    const Workspace& ws = ctx->ws;
+    if (pass == 0) {
+        ProfScope prof(ctx, K_SEL_HIST0, st);
+        hipLaunchKernelGGL((k_sel_hist<0, 7, true>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr);
+    } else if (pass == 1) {
+        ProfScope prof(ctx, K_SEL_HIST1, st);
+        hipLaunchKernelGGL((k_sel_hist<1, 7, true>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr);
+    } else {
+        ProfScope prof(ctx, K_SEL_HIST2, st);
+        hipLaunchKernelGGL((k_sel_hist<2, 7, true>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr);
+    }
+}
+
+void launch_select_mask_paged(kvtrim_ctx* ctx, const float* score, const SelTables& tb, int n_pages,
+                              uint8_t* keep, int32_t* kept, hipStream_t st) {
+    ProfScope prof(ctx, K_SEL_MASK, st);
+    hipLaunchKernelGGL((k_sel_mask<7, true>), dim3(n_pages), dim3(SEL_THREADS), 0, st, score, ctx->shape, ctx->ws, tb,
+                       keep, kept);
+}
+
 kvtrim_status launch_select(kvtrim_ctx* ctx, const CacheView& c, const float* score, const int64_t* budget,
                             uint8_t* keep, int32_t* kept, uint32_t* thr, hipStream_t st) {
     const Shape& sh = ctx->shape;
@@ -308,18 +338,22 @@ kvtrim_status launch_select(kvtrim_ctx* ctx, const CacheView& c, const float* sc
     const int64_t max_chunks = c.cap / SEL_CHUNK + sh.nseg;      // bound on the chunk count
     const int n_chunk_blocks = (int)max_chunks;
     const int hist_blocks = (int)(max_chunks < HIST_BLOCKS ? (max_chunks < 1 ? 1 : max_chunks) : HIST_BLOCKS);
+    SelTables tb;
+    tb.desc = ws.sel_desc;
+    tb.prefix = ws.sel_chunk_prefix;
+    tb.pos = nullptr;
     { ProfScope prof(ctx, K_SEL_PLAN, st);
       hipLaunchKernelGGL(k_sel_plan, dim3(1 + PLAN_ZERO_BLOCKS), dim3(1024), 0, st, c, sh, budget, ws, kept, hist_blocks); }
     { ProfScope prof(ctx, K_SEL_HIST0, st);
-      hipLaunchKernelGGL(k_sel_hist<0>, dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, thr); }
+      hipLaunchKernelGGL((k_sel_hist<0, SEL_SHIFT, false>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr); }
     { ProfScope prof(ctx, K_SEL_HIST1, st);
-      hipLaunchKernelGGL(k_sel_hist<1>, dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, thr); }
+      hipLaunchKernelGGL((k_sel_hist<1, SEL_SHIFT, false>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr); }
     { ProfScope prof(ctx, K_SEL_HIST2, st);
-      hipLaunchKernelGGL(k_sel_hist<2>, dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, thr); }
+      hipLaunchKernelGGL((k_sel_hist<2, SEL_SHIFT, false>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr); }
     { ProfScope prof(ctx, K_SEL_COUNT, st);
-      hipLaunchKernelGGL(k_sel_count, dim3(n_chunk_blocks < 256 ? n_chunk_blocks : 256), dim3(CNT_THREADS), 0, st, score, sh, ws, kept); }
+      hipLaunchKernelGGL(k_sel_count, dim3(n_chunk_blocks < 256 ? n_chunk_blocks : 256), dim3(CNT_THREADS), 0, st, score, sh, ws, tb, kept); }
     { ProfScope prof(ctx, K_SEL_MASK, st);
-      hipLaunchKernelGGL(k_sel_mask, dim3(n_chunk_blocks), dim3(SEL_THREADS), 0, st, score, sh, ws, keep, kept); }
+      hipLaunchKernelGGL((k_sel_mask<SEL_SHIFT, false>), dim3(n_chunk_blocks), dim3(SEL_THREADS), 0, st, score, sh, ws, tb, keep, kept); }
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;
 }

@@ -33,7 +33,7 @@ static bool config_ok(const kvtrim_config* c) {
 }
 
 struct Layout {
-    size_t off[16];
+    size_t off[24];
     size_t total;
     int64_t max_sel_chunks, max_cmp_chunks, max_att_chunks;
 };
@@ -74,6 +74,11 @@ static Layout layout_of(const kvtrim_config* c) {
     l.off[13] = bump(cur, 256);                                                // err
     l.off[14] = bump(cur, (nseg + 1) * sizeof(int64_t));                       // sel_entry_prefix
     l.off[15] = bump(cur, HIST_BLOCKS_MAX * sizeof(int4));                     // sel_blk
+    l.off[16] = bump(cur, (size_t)nseg * sizeof(int32_t));                     // tie_cnt
+    l.off[17] = bump(cur, (size_t)nseg * sizeof(int32_t));                     // tie_mode
+    l.off[18] = bump(cur, (size_t)nseg * sizeof(int32_t));                     // tie_thr
+    l.off[19] = bump(cur, (size_t)nseg * sizeof(int64_t));                     // pg_seg_start
+    l.off[20] = bump(cur, (size_t)nseg * sizeof(int32_t));                     // pg_seg_len
     l.total = (cur + 255) & ~(size_t)255;
     return l;
 }
@@ -179,6 +184,11 @@ kvtrim_status kvtrim_create(kvtrim_ctx** out, const kvtrim_config* cfg) {
     w.err = (int32_t*)(b + l.off[13]);
     w.sel_entry_prefix = (int64_t*)(b + l.off[14]);
     w.sel_blk = (int4*)(b + l.off[15]);
+    w.tie_cnt = (int32_t*)(b + l.off[16]);
+    w.tie_mode = (int32_t*)(b + l.off[17]);
+    w.tie_thr = (int32_t*)(b + l.off[18]);
+    w.pg_seg_start = (int64_t*)(b + l.off[19]);
+    w.pg_seg_len = (int32_t*)(b + l.off[20]);
     w.max_sel_chunks = l.max_sel_chunks;
     w.max_cmp_chunks = l.max_cmp_chunks;
     w.max_att_chunks = l.max_att_chunks;
@@ -201,7 +211,8 @@ static void free_profile(kvtrim_ctx* ctx) {
 
 static const char* const kernel_names[KVTRIM_N_KERNELS] = {
     "k_score", "k_sel_plan", "k_sel_hist<0>", "k_sel_hist<1>", "k_sel_hist<2>", "k_sel_count", "k_sel_mask",
-    "k_cmp_scan", "k_cmp_copy", "k_att_plan", "k_att_partial", "k_att_combine", "k_append", "k_cmp_attn", "k_occupancy"};
+    "k_cmp_scan", "k_cmp_copy", "k_att_plan", "k_att_partial", "k_att_combine", "k_append", "k_cmp_attn", "k_occupancy",
+    "k_pg_init", "k_pg_append", "k_pg_score", "k_pg_plan", "k_pg_count", "k_pg_evict", "k_pg_tidy", "k_pg_att_plan"};
 
 const char* kvtrim_kernel_name(int32_t id) { return id >= 0 && id < KVTRIM_N_KERNELS ? kernel_names[id] : nullptr; }
 

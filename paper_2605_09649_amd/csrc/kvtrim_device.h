@@ -55,6 +55,20 @@ __device__ __forceinline__ T block_sum(T v, T* lds) {
     return s;
 }
 
+// "Last block done" detection, called by one thread per block after the block's results are
+// written.  Device-scope atomics on ONE address are served one after the other (tens of
+// nanoseconds each), so 256 blocks do not meet on one counter: 16 group counters first, then the
+// last block of each group on the top-level counter.  counters: [0] top level, [1..16] groups.
+__device__ __forceinline__ bool arrive_last(uint32_t* counters) {
+    __threadfence();
+    const unsigned grp = blockIdx.x & 15u;
+    const unsigned gsize = (gridDim.x - grp + 15u) / 16u;        // blocks with this group number
+    if (atomicAdd(&counters[1 + grp], 1u) != gsize - 1) return false;
+    __threadfence();
+    const unsigned ngroups = gridDim.x < 16u ? gridDim.x : 16u;
+    return atomicAdd(&counters[0], 1u) == ngroups - 1;
+}
+
 // Chunk table of a ragged cache, built by ONE block (blockDim.x <= 1024): segment g with
 // in_range(g) is cut into ceil(seg_len[g] / chunk) chunks (none for the other segments);
 // prefix[g] = first chunk of segment g, prefix[nseg] = number of chunks, desc[c] = entries and

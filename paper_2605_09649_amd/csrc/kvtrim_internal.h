@@ -70,12 +70,26 @@ struct ChunkDesc {
     int32_t seg;
 };
 
+// The chunk table a selection pass walks: the context's own table of a ragged cache, or one
+// chunk per page of a paged cache (then `pos` marks the live slots).
+struct SelTables {
+    const ChunkDesc* desc;
+    const int32_t* prefix;       // [nseg+1] first chunk of each segment
+    const int32_t* pos;          // paged only
+};
+
 struct Workspace {
     // selection
     int32_t* sel_chunk_prefix;   // [nseg+1] first chunk of each segment
     ChunkDesc* sel_desc;         // [max_sel_chunks]
     int64_t* sel_entry_prefix;   // [nseg+1] entries before each segment
     int4* sel_blk;               // [HIST_BLOCKS_MAX] per histogram block: first chunk, end chunk, first and last sequence
+    // paged selection: ties at the threshold, per segment
+    int32_t* tie_cnt;            // [nseg]
+    int32_t* tie_mode;           // [nseg] 0: no tie survives, 1: all, 2: those with pos <= tie_thr
+    int32_t* tie_thr;            // [nseg]
+    int64_t* pg_seg_start;       // [nseg] segment table of the page-aligned compaction that builds a paged cache
+    int32_t* pg_seg_len;         // [nseg]
     uint32_t* hist;              // [3][HIST_REPLICAS][n_seq][RADIX_BINS]
     SelState* sel;               // [n_seq]
     uint32_t* done;              // [DONE_WORDS] "last block" counters: per pass one top-level and 16 group counters
@@ -98,7 +112,8 @@ struct Workspace {
 namespace kvtrim {
 enum KernelId {
     K_SCORE = 0, K_SEL_PLAN, K_SEL_HIST0, K_SEL_HIST1, K_SEL_HIST2, K_SEL_COUNT, K_SEL_MASK,
-    K_CMP_SCAN, K_CMP_COPY, K_ATT_PLAN, K_ATT_PARTIAL, K_ATT_COMBINE, K_APPEND, K_CMP_ATTN, K_OCCUPANCY, K_COUNT
+    K_CMP_SCAN, K_CMP_COPY, K_ATT_PLAN, K_ATT_PARTIAL, K_ATT_COMBINE, K_APPEND, K_CMP_ATTN, K_OCCUPANCY,
+    K_PG_INIT, K_PG_APPEND, K_PG_SCORE, K_PG_PLAN, K_PG_COUNT, K_PG_EVICT, K_PG_TIDY, K_PG_ATT_PLAN, K_COUNT
 };
 static_assert(K_COUNT == KVTRIM_N_KERNELS, "kernel table out of step with the header");
 }  // namespace kvtrim
@@ -132,6 +147,17 @@ kvtrim_status launch_compact(kvtrim_ctx*, const CacheView& src, const uint8_t* k
                              const CacheViewMut& dst, int32_t reserve, hipStream_t);
 kvtrim_status launch_attn(kvtrim_ctx*, const CacheView&, const uint16_t* q, const int32_t* soft_now,
                           int32_t layer_begin, int32_t layer_end, float scale, float* out, float* lse, hipStream_t);
+void launch_select_passes_paged(kvtrim_ctx*, const float* score, const SelTables&, int hist_blocks, int pass,
+                                uint32_t* thr, hipStream_t);
+void launch_select_mask_paged(kvtrim_ctx*, const float* score, const SelTables&, int n_pages, uint8_t* keep,
+                              int32_t* kept, hipStream_t);
+kvtrim_status launch_attn_paged(kvtrim_ctx*, const CacheView& pool, const uint16_t* q, int n_pages,
+                                int32_t layer_begin, int32_t layer_end, float scale, float* out, float* lse,
+                                hipStream_t);
+void launch_cmp_scan_aligned(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const int32_t* kept,
+                             const CacheViewMut& dst, int32_t reserve, int32_t align, hipStream_t);
+kvtrim_status launch_cmp_copy(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const CacheViewMut& dst,
+                              hipStream_t);
 kvtrim_status launch_occupancy(kvtrim_ctx*, const CacheView&, const int32_t* now, double* occ, hipStream_t);
 void launch_cmp_scan(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const int32_t* kept,
                      const CacheViewMut& dst, int32_t reserve, hipStream_t);

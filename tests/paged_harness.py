@@ -1,0 +1,213 @@
+"""Runs the decode loop on the paged layout (append -> score -> select -> evict -> attend, no K/V
+moved) through the C ABI on the GPU, next to the CPU oracle's ragged loop on the same inputs.
+
+A paged segment holds its entries in no particular order, so the comparison goes through the
+positions (unique inside a segment): the live slots of every segment, sorted by position, must be
+the oracle's segment entry for entry, bit for bit."""
+import math
+
+import numpy as np
+import torch
+
+import kvtrim_inputs as ki
+import oracle
+import paper_2605_09649_amd as kv
+from harness import attn_error
+from helpers import bf16_bits, host_cache, live_mask
+
+P = kv.PAGE_SIZE
+
+
+class PagedHost:
+    """Host copy of the bookkeeping (and, on request, the rows) of a paged cache."""
+
+    def __init__(self, pc, rows=True):
+        self.n_pages, self.max_pps, self.nseg = pc.n_pages, pc.max_pages_per_seg, pc.nseg
+        self.bt = pc.block_table.cpu().numpy()
+        self.seg_pages = pc.seg_pages.cpu().numpy()
+        self.seg_live = pc.seg_live.cpu().numpy()
+        self.owner = pc.page_owner.cpu().numpy()
+        self.page_live = pc.page_live.cpu().numpy()
+        self.free_list = pc.free_list.cpu().numpy()
+        self.n_free = int(pc.n_free.cpu().numpy()[0])
+        self.pos = pc.pos.cpu().numpy()
+        self.log_beta = pc.log_beta.cpu().numpy()
+        self.log_tail = None if pc.log_tail is None else pc.log_tail.cpu().numpy()
+        if rows:
+            self.k, self.v = bf16_bits(pc.k), bf16_bits(pc.v)
+
+    def structure_problems(self):
+        """Everything that must hold between two calls, as a list of findings (empty = fine)."""
+        bad = []
+        sp = self.seg_pages
+        if (sp < 0).any() or (sp > self.max_pps).any():
+            return ["seg_pages out of range"]
+        live_slots = (self.pos.reshape(self.n_pages, P) >= 0).sum(1)
+        seen = np.full(self.n_pages, -1, np.int64)
+        for g in range(self.nseg):
+            pages = self.bt[g, :sp[g]]
+            if (pages < 0).any() or (pages >= self.n_pages).any():
+                bad.append(f"segment {g}: page id out of range")
+                continue
+            if (seen[pages] >= 0).any() or len(np.unique(pages)) != len(pages):
+                bad.append(f"segment {g}: page listed twice")
+            seen[pages] = g
+            if (self.owner[pages] != g).any():
+                bad.append(f"segment {g}: owner mismatch")
+            if (live_slots[pages] < 1).any():
+                bad.append(f"segment {g}: empty page in the table")
+            if int(live_slots[pages].sum()) != int(self.seg_live[g]):
+                bad.append(f"segment {g}: seg_live {self.seg_live[g]} != {int(live_slots[pages].sum())}")
+        if not np.array_equal(self.page_live[seen >= 0], live_slots[seen >= 0]):
+            bad.append("page_live differs from the slots")
+        free = np.flatnonzero(seen < 0)
+        if (self.owner[free] != -1).any() or (self.page_live[free] != 0).any() or (live_slots[free] != 0).any():
+            bad.append("free page with an owner or live slots")
+        if self.n_free != len(free):
+            bad.append(f"n_free {self.n_free} != {len(free)}")
+        elif not np.array_equal(np.sort(self.free_list[:self.n_free]), free):
+            bad.append("free list differs from the set of free pages")
+        return bad
+
+    def ordered_slots(self):
+        """Live slots of all segments, segment by segment, each sorted by position; and counts."""
+        idx, counts = [], []
+        lane = np.arange(P, dtype=np.int64)[None, :]
+        for g in range(self.nseg):
+            pages = self.bt[g, :self.seg_pages[g]].astype(np.int64)
+            slots = (pages[:, None] * P + lane).ravel()
+            slots = slots[self.pos[slots] >= 0]
+            slots = slots[np.argsort(self.pos[slots], kind="stable")]
+            idx.append(slots)
+            counts.append(len(slots))
+        return (np.concatenate(idx) if idx else np.zeros(0, np.int64)), np.array(counts, np.int32)
+
+    def equals(self, hc):
+        """Same entries per segment as the oracle's ragged cache hc."""
+        idx, counts = self.ordered_slots()
+        if not np.array_equal(counts, hc.seg_len):
+            return False
+        m = live_mask(hc)
+        ok = (np.array_equal(self.pos[idx], hc.pos[m])
+              and np.array_equal(self.log_beta[idx].view(np.uint32), hc.log_beta[m].view(np.uint32))
+              and np.array_equal(self.k[idx], hc.k[m]) and np.array_equal(self.v[idx], hc.v[m]))
+        if hc.log_tail is not None:
+            ok = ok and self.log_tail is not None and np.array_equal(self.log_tail[idx].view(np.uint32),
+                                                                      hc.log_tail[m].view(np.uint32))
+        return bool(ok)
+
+
+def attn_result(out_gpu, lse_gpu, out_ref, lse_ref):
+    fin = np.isfinite(lse_ref)
+    return {"attn_err": attn_error(out_gpu, out_ref),
+            "lse_err": float(np.abs(lse_gpu[fin] - lse_ref[fin]).max()) if fin.any() else 0.0,
+            "lse_inf_equal": bool(np.array_equal(np.isneginf(lse_gpu), np.isneginf(lse_ref)))}
+
+
+def ties_overflow(w, hc, score_ref, live, thr_ref, budget_np):
+    """True if in some sequence the entries at or above the threshold outnumber the budget, i.e.
+    the ties at the threshold had to be ranked by (layer, head, position)."""
+    per_seq = w.n_layers * w.n_kv_heads
+    u = score_ref.view(np.uint32)
+    key = np.where(u & np.uint32(0x80000000), ~u, u | np.uint32(0x80000000))
+    seq_of = np.zeros(hc.cap, np.int64)
+    for g, (s, n) in enumerate(zip(hc.seg_start, hc.seg_len)):
+        seq_of[s:s + n] = g // per_seq
+    for seq in range(w.n_seq):
+        m = live & (seq_of == seq)
+        if 0 < budget_np[seq] < int(m.sum()) and int((key[m] >= thr_ref[seq]).sum()) > int(budget_np[seq]):
+            return True
+    return False
+
+
+def run_paged_both(w, budgets, device="cuda:0", cache_dict=None, now0=None, n_pages=None, max_pps=None, horizon=1,
+                   tweak_new=None):
+    """budgets: one per-sequence budget list per step; step 0 selects on the ragged prefill cache
+    and builds the pages, the later steps run on the pages.  tweak_new(step, inputs) may edit the
+    generated inputs of a step (used to plant ties).  Returns one dict of findings per step."""
+    reserve = 1
+    if cache_dict is None:
+        cache_dict = ki.prefill_cache(w, reserve=reserve)
+        now0 = [t - 1 for t in w.prefill]
+    cache_dict = ki.with_horizon(cache_dict, horizon)
+    hc = host_cache(w, cache_dict)
+    src = kv.Cache.from_dict(cache_dict, device)
+    per_seq = w.n_layers * w.n_kv_heads
+    steps = len(budgets)
+    if n_pages is None:
+        most = max(int(sum(b)) for b in budgets)
+        n_pages = (min(most, int(cache_dict["seg_len"].sum()) + steps * w.nseg) + P - 1) // P + 2 * w.nseg + 8
+    if max_pps is None:
+        max_pps = n_pages
+    slots = n_pages * P
+    ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, max(src.cap, slots))
+    pc = kv.PagedCache(w.nseg, w.head_dim, n_pages, max_pps, device, with_tail=horizon != 1)
+    cap = max(src.cap, slots)
+    score = torch.zeros(cap, dtype=torch.float32, device=device)
+    keep = torch.zeros(cap, dtype=torch.uint8, device=device)
+    kept = torch.zeros(w.nseg, dtype=torch.int32, device=device)
+    thr = torch.zeros(w.n_seq, dtype=torch.int32, device=device)
+    out = torch.zeros(w.n_seq, w.n_layers, w.n_q_heads, w.head_dim, dtype=torch.float32, device=device)
+    lse = torch.zeros(w.n_seq, w.n_layers, w.n_q_heads, dtype=torch.float32, device=device)
+    scale = 1.0 / math.sqrt(w.head_dim)
+    now = np.array(now0, np.int32)
+    dst_cap = int(cache_dict["seg_len"].sum()) + (steps + reserve) * w.nseg + 8
+    results = []
+    for step in range(steps):
+        inp = ki.decode_inputs(w, step, horizon=horizon)
+        if tweak_new is not None:
+            tweak_new(step, inp)
+        now = now + 1
+        pos_new = np.repeat(now, per_seq).astype(np.int32)
+        budget_np = np.array(list(budgets[step]), np.int64)
+        lt_new = None if horizon == 1 else inp["log_tail_new"]
+        # ---- oracle: ragged loop
+        oracle.append(hc, bf16_bits(inp["k_new"]), bf16_bits(inp["v_new"]), inp["log_beta_new"].numpy(), pos_new,
+                      log_tail_new=None if lt_new is None else lt_new.numpy())
+        score_ref = oracle.score(hc, now)
+        keep_ref, kept_ref, thr_ref = oracle.select(hc, score_ref, budget_np)
+        hc_next = oracle.compact(hc, keep_ref, dst_cap, reserve)
+        out_ref, lse_ref = oracle.attend(hc_next, bf16_bits(inp["q"]), scale)
+        live = live_mask(hc)
+        # ---- GPU
+        d = {k: v.to(device) for k, v in inp.items()}
+        now_dev, pos_dev = torch.from_numpy(now).to(device), torch.from_numpy(pos_new).to(device)
+        budget_dev = torch.from_numpy(budget_np).to(device)
+        res = {"step": step}
+        if step == 0:
+            kv.kvtrim_append(ctx, src, d["k_new"], d["v_new"], d["log_beta_new"], pos_dev, 1,
+                             log_tail_new=d.get("log_tail_new"))
+            kv.kvtrim_score(ctx, src, now_dev, score)
+            kv.kvtrim_select_global(ctx, src, score, budget_dev, keep, kept, thr)
+            kv.kvtrim_paged_build(ctx, src, keep, kept, pc)
+            res["score_equal"] = bool(np.array_equal(score[:hc.cap].cpu().numpy()[live].view(np.uint32),
+                                                     score_ref[live].view(np.uint32)))
+            res["keep_equal"] = bool(np.array_equal(keep[:hc.cap].cpu().numpy()[live], keep_ref[live]))
+        else:
+            kv.kvtrim_paged_append(ctx, pc, d["k_new"], d["v_new"], d["log_beta_new"], pos_dev,
+                                   log_tail_new=d.get("log_tail_new"))
+            kv.kvtrim_paged_score(ctx, pc, now_dev, score)
+            kv.kvtrim_paged_select(ctx, pc, score, budget_dev, keep, kept, thr)
+            res["status_select"] = kv.kvtrim_poll_error(ctx)
+            pre = PagedHost(pc, rows=False)
+            res["structure_pre"] = pre.structure_problems()
+            idx, counts = pre.ordered_slots()
+            same = np.array_equal(counts, hc.seg_len)
+            res["score_equal"] = bool(same and np.array_equal(score.cpu().numpy()[idx].view(np.uint32),
+                                                              score_ref[live].view(np.uint32)))
+            res["keep_equal"] = bool(same and np.array_equal(keep.cpu().numpy()[idx], keep_ref[live]))
+            kv.kvtrim_paged_evict(ctx, pc, keep)
+        kv.kvtrim_paged_attn(ctx, pc, d["q"], 0, w.n_layers, scale, out, lse)
+        res["status"] = kv.kvtrim_poll_error(ctx)
+        res["kept_equal"] = bool(np.array_equal(kept.cpu().numpy(), kept_ref)
+                                 and np.array_equal(thr.cpu().numpy().view(np.uint32), thr_ref))
+        ph = PagedHost(pc)
+        res["structure"] = ph.structure_problems()
+        res["cache_equal"] = ph.equals(hc_next)
+        res.update(attn_result(out.cpu().numpy(), lse.cpu().numpy(), out_ref, lse_ref))
+        res["kept_total"] = int(kept_ref.sum())
+        res["pages_in_use"] = int(ph.seg_pages.sum())
+        res["ties_overflow"] = ties_overflow(w, hc, score_ref, live, thr_ref, budget_np)
+        results.append(res)
+        hc = hc_next
+    return results

@@ -1,0 +1,179 @@
+"""GPU parity of the paged layout (Sec. 4.2, implementation details: pages, block tables, per-head
+variable lengths, eviction without moving K/V) against the CPU oracle's ragged loop.
+
+Scores, the keep mask, the survivors of every segment and the threshold are compared bit for bit
+(entries matched through their positions); attention within 5e-3; and the page bookkeeping must
+be consistent after every call.
+"""
+import numpy as np
+import pytest
+import torch
+
+import kvtrim_inputs as ki
+import paper_2605_09649_amd as kv
+from paged_harness import P, PagedHost, run_paged_both
+
+pytestmark = pytest.mark.gpu
+ATTN_TOL = 5e-3
+DEV = "cuda:0"
+
+
+def check(results):
+    for r in results:
+        assert r["status"] == 0 and r.get("status_select", 0) == 0, r
+        assert r["structure"] == [] and r.get("structure_pre", []) == [], r
+        assert r["score_equal"], (r["step"], "score bits differ")
+        assert r["keep_equal"] and r["kept_equal"], (r["step"], "selection differs")
+        assert r["cache_equal"], (r["step"], "surviving entries differ")
+        assert r["attn_err"] <= ATTN_TOL, r
+        assert r["lse_err"] <= 2e-3 and r["lse_inf_equal"], r
+
+
+def wl(S, L, H, G, D):
+    return ki.Workload("t", 0, S, L, H, G * H, D, (0,) * S, (0,) * S, 1, 3.0, 1.5)
+
+
+def test_tiny_workload_paged_loop():
+    w = ki.workload("tiny")                       # L4 H4 G2 D64, 2048 prefilled, B = 1024
+    check(run_paged_both(w, [w.budget] * 12, device=DEV))
+
+
+@pytest.mark.parametrize("name,prefill,steps", [("llama", 700, 4), ("long", 900, 4), ("vlm", 640, 4),
+                                                ("multiturn", 600, 3)])
+def test_scaled_down_workloads_paged(name, prefill, steps):
+    w = ki.workload(name, prefill=prefill)
+    check(run_paged_both(w, [w.budget] * steps, device=DEV))
+
+
+@pytest.mark.parametrize("S,L,H,G,D", [(1, 2, 2, 1, 128), (2, 2, 1, 7, 128), (1, 1, 3, 8, 64), (3, 1, 2, 3, 64),
+                                       (1, 2, 2, 5, 128), (1, 1, 2, 6, 128)])
+def test_ragged_segments_with_empty_ones_paged(S, L, H, G, D):
+    w = wl(S, L, H, G, D)
+    rng = np.random.default_rng(S * 1000 + G * 10 + D)
+    seg_len = rng.integers(0, 3000, w.nseg)
+    seg_len[rng.integers(0, w.nseg)] = 0
+    seg_len[rng.integers(0, w.nseg)] = 5 * P                      # ends exactly on a page boundary
+    c, now = ki.ragged_cache(w, seg_len, reserve=1, salt=G)
+    per_seq = [int(seg_len[s * L * H:(s + 1) * L * H].sum()) for s in range(S)]
+    budget = [max(1, n // 3) for n in per_seq]
+    check(run_paged_both(w, [budget] * 4, device=DEV, cache_dict=c, now0=now.numpy()))
+
+
+def test_pages_are_freed_and_taken_again():
+    # the budget shrinks (pages empty out and return to the free list), then grows past the cache
+    # size (nothing is evicted, every full segment takes a page from the free list)
+    w = wl(1, 2, 3, 2, 64)
+    seg_len = [700, 130, 0, 1024, 255, 256]
+    c, now = ki.ragged_cache(w, seg_len, reserve=1, salt=11)
+    total = sum(seg_len)
+    budgets = [[total], [total // 2], [total // 8], [40], [10 ** 6], [10 ** 6], [10 ** 6], [50], [10 ** 6]]
+    budgets += [[10 ** 6]] * 130 + [[3], [0], [10 ** 6], [10 ** 6]]
+    res = run_paged_both(w, budgets, device=DEV, cache_dict=c, now0=now.numpy(), n_pages=40)
+    check(res)
+    pages = [r["pages_in_use"] for r in res]
+    assert min(pages[:9]) < pages[0] and pages[-3] == 0 and pages[-1] == w.nseg
+    assert max(pages) > pages[8]                                   # pages were taken from the free list again
+
+
+@pytest.mark.parametrize("horizon", [2, 0])
+def test_lookahead_horizon_paged(horizon):
+    w = ki.workload("tiny", prefill=700)
+    check(run_paged_both(w, [w.budget] * 4, device=DEV, horizon=horizon))
+
+
+def test_ties_at_the_threshold_are_ranked_by_layer_head_position():
+    # beta = 1 (log beta = 0) for most entries: their scores are all 0, the maximum, and the budget
+    # cuts through them, so the tie rule decides - whole segments first, in one segment by position.
+    # After the first eviction the slots of a segment are no longer in position order.
+    w = wl(2, 2, 2, 2, 64)
+    seg_len = [600, 300, 257, 900, 128, 0, 640, 1000]
+    c, now = ki.ragged_cache(w, seg_len, reserve=1, salt=5)
+    g = torch.Generator().manual_seed(1)
+    lb = c["log_beta"]
+    lb[torch.rand(lb.shape, generator=g) < 0.8] = 0.0
+
+    def plant(step, inp):
+        if step % 2 == 0:
+            inp["log_beta_new"][:] = 0.0
+
+    budgets = [[1500, 1200], [900, 1100], [901, 600], [450, 601], [451, 100], [100, 99], [7, 98]]
+    res = run_paged_both(w, budgets, device=DEV, cache_dict=c, now0=now.numpy(), tweak_new=plant)
+    check(res)
+    assert sum(r["ties_overflow"] for r in res[1:]) >= 5
+
+
+def test_budget_zero_and_above_full_per_sequence():
+    w = wl(3, 1, 2, 2, 128)
+    seg_len = [300, 200, 500, 1, 129, 640]
+    c, now = ki.ragged_cache(w, seg_len, reserve=1, salt=2)
+    budgets = [[400, 10 ** 6, 600], [0, 10 ** 6, 300], [5, 0, 10 ** 6], [10 ** 6, 10 ** 6, 0]]
+    check(run_paged_both(w, budgets, device=DEV, cache_dict=c, now0=now.numpy()))
+
+
+def _small_setup(n_pages, max_pps, seg_len=(300, 200)):
+    w = wl(1, 1, 2, 2, 64)
+    c, now = ki.ragged_cache(w, list(seg_len), reserve=1, salt=9)
+    src = kv.Cache.from_dict(c, DEV)
+    ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, max(src.cap, n_pages * P))
+    pc = kv.PagedCache(w.nseg, w.head_dim, n_pages, max_pps, DEV)
+    keep = torch.ones(src.cap, dtype=torch.uint8, device=DEV)
+    kept = torch.tensor(list(seg_len), dtype=torch.int32, device=DEV)
+    return w, ctx, src, pc, keep, kept
+
+
+def test_device_side_errors_of_the_paged_calls():
+    # not enough pages for the build
+    w, ctx, src, pc, keep, kept = _small_setup(n_pages=4, max_pps=8)
+    kv.kvtrim_paged_build(ctx, src, keep, kept, pc)
+    assert kv.kvtrim_poll_error(ctx) == -4
+    # a segment needs more pages than its block table holds
+    w, ctx, src, pc, keep, kept = _small_setup(n_pages=8, max_pps=2)
+    kv.kvtrim_paged_build(ctx, src, keep, kept, pc)
+    assert kv.kvtrim_poll_error(ctx) == -4
+    # kept that disagrees with the mask
+    w, ctx, src, pc, keep, kept = _small_setup(n_pages=8, max_pps=8)
+    kept[0] = 299
+    kv.kvtrim_paged_build(ctx, src, keep, kept, pc)
+    assert kv.kvtrim_poll_error(ctx) == -5
+    # append with every page full and none free: the cache stays as it was
+    w, ctx, src, pc, keep, kept = _small_setup(n_pages=3, max_pps=8, seg_len=(256, 128))
+    kv.kvtrim_paged_build(ctx, src, keep, kept, pc)
+    assert kv.kvtrim_poll_error(ctx) == 0
+    before = PagedHost(pc)
+    assert before.structure_problems() == [] and before.n_free == 0
+    inp = {k: v.to(DEV) for k, v in ki.decode_inputs(w, 0).items()}
+    pos_new = torch.full((w.nseg,), 5000, dtype=torch.int32, device=DEV)
+    kv.kvtrim_paged_append(ctx, pc, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos_new)
+    assert kv.kvtrim_poll_error(ctx) == -4
+    after = PagedHost(pc)
+    assert after.structure_problems() == [] and np.array_equal(after.pos, before.pos)
+    # a block table that is full
+    w, ctx, src, pc, keep, kept = _small_setup(n_pages=6, max_pps=2, seg_len=(256, 100))
+    kv.kvtrim_paged_build(ctx, src, keep, kept, pc)
+    assert kv.kvtrim_poll_error(ctx) == 0
+    kv.kvtrim_paged_append(ctx, pc, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos_new)
+    assert kv.kvtrim_poll_error(ctx) == -4
+    after = PagedHost(pc)
+    assert after.structure_problems() == []
+    assert list(after.seg_live) == [256, 101]                     # the other segment took its token
+
+
+def test_host_side_argument_checks_of_the_paged_calls():
+    w, ctx, src, pc, keep, kept = _small_setup(n_pages=8, max_pps=8)
+    score = torch.zeros(pc.slots, dtype=torch.float32, device=DEV)
+    now = torch.zeros(1, dtype=torch.int32, device=DEV)
+    with pytest.raises(kv.KvtrimError):
+        kv.kvtrim_paged_score(ctx, pc, None, score)
+    with pytest.raises(kv.KvtrimError):
+        kv.kvtrim_paged_build(ctx, src, None, kept, pc)
+    big = kv.PagedCache(w.nseg, w.head_dim, 64, 8, DEV)           # more slots than the context was made for
+    with pytest.raises(kv.KvtrimError):
+        kv.kvtrim_paged_score(ctx, big, now, score)
+    tail = kv.PagedCache(w.nseg, w.head_dim, 8, 8, DEV, with_tail=True)
+    with pytest.raises(kv.KvtrimError):
+        kv.kvtrim_paged_build(ctx, src, keep, kept, tail)         # horizon constant on one side only
+    q = torch.zeros(1, 1, 4, 64, dtype=torch.bfloat16, device=DEV)
+    out = torch.zeros(1, 1, 4, 64, dtype=torch.float32, device=DEV)
+    with pytest.raises(kv.KvtrimError):
+        kv.kvtrim_paged_attn(ctx, pc, q, 0, 2, 0.125, out)        # layer range beyond the model
+    assert kv.kvtrim_poll_error(ctx) == 0
