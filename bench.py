@@ -59,7 +59,15 @@ def main():
                     help="also run one plain 1 GiB device copy, the known-size reference for rocprofv3 --pmc counters")
     ap.add_argument("--unfused", action="store_true",
                     help="run stages 3 and 4 as two calls (kvtrim_compact, kvtrim_decode_attn) instead of the fused one")
+    ap.add_argument("--paged", action="store_true",
+                    help="steady state on the paged layout: eviction frees slots of fixed-size pages and moves no K/V "
+                         "(paged_append, paged_score, paged_select, paged_evict, paged_attn)")
+    ap.add_argument("--kernel-times", action="store_true",
+                    help="bracket every kernel with HIP events and print the per-kernel averages to stderr "
+                         "(the events add a little to ms_per_step)")
     args = ap.parse_args()
+    if args.paged and args.unfused:
+        ap.error("--paged and --unfused exclude each other")
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
@@ -86,9 +94,17 @@ def main():
     B = sum(w.budget)
     dst_cap = min(B, total0 + n_steps * w.nseg) + w.nseg * reserve + 8
     src = kv.Cache.from_dict(pre, dev)
-    ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, max(src.cap, dst_cap))
-    spare = [kv.Cache.empty(w.nseg, w.head_dim, dst_cap, dev, with_tail=args.horizon != 1) for _ in range(2)]
+    spare, pc = [], None
+    if args.paged:
+        # room for the budget, one partly filled page per segment, and the pages that segments take while
+        # their own still hold scattered free slots elsewhere
+        n_pages = (min(B, total0 + n_steps * w.nseg) + kv.PAGE_SIZE - 1) // kv.PAGE_SIZE + 3 * w.nseg + 64
+        pc = kv.PagedCache(w.nseg, w.head_dim, n_pages, n_pages, dev, with_tail=args.horizon != 1)
+        dst_cap = n_pages * kv.PAGE_SIZE
+    else:
+        spare = [kv.Cache.empty(w.nseg, w.head_dim, dst_cap, dev, with_tail=args.horizon != 1) for _ in range(2)]
     cap = max(src.cap, dst_cap)
+    ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, cap)
     score = torch.zeros(cap, dtype=torch.float32, device=dev)
     keep = torch.zeros(cap, dtype=torch.uint8, device=dev)
     kept = torch.zeros(w.nseg, dtype=torch.int32, device=dev)
@@ -114,10 +130,23 @@ def main():
     def step(s):
         inp = inputs[s]
         cur = state["src"]
+        if args.paged and s > 0:
+            kv.kvtrim_paged_append(ctx, pc, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos_news[s],
+                                   log_tail_new=inp.get("log_tail_new"))
+            kv.kvtrim_paged_score(ctx, pc, nows[s], score)
+            kv.kvtrim_paged_select(ctx, pc, score, budget, keep, kept, thr)
+            kv.kvtrim_paged_evict(ctx, pc, keep)
+            kv.kvtrim_paged_attn(ctx, pc, inp["q"], 0, w.n_layers, scale, out, lse)
+            return
         kv.kvtrim_append(ctx, cur, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos_news[s], 1,
                          log_tail_new=inp.get("log_tail_new"))
         kv.kvtrim_score(ctx, cur, nows[s], score)
         kv.kvtrim_select_global(ctx, cur, score, budget, keep, kept, thr)
+        if args.paged:                          # first step: the survivors of the prefill go into pages
+            kv.kvtrim_paged_build(ctx, cur, keep, kept, pc)
+            kv.kvtrim_paged_attn(ctx, pc, inp["q"], 0, w.n_layers, scale, out, lse)
+            state["src"] = None
+            return
         dst = spare[state["flip"]]
         if args.unfused:
             kv.kvtrim_compact(ctx, cur, keep, kept, dst, reserve)
@@ -154,6 +183,8 @@ def main():
 
     # ---- timed region: exactly K steps; the dominant kernels are bracketed by HIP events on the launch stream
     mask = (1 << 8) | (1 << 10) | (1 << 13)   # k_cmp_copy, k_att_partial, k_cmp_attn
+    if args.kernel_times:
+        mask = (1 << kv.binding.N_KERNELS) - 1   # every kernel (the events then add to the step time)
     kv.kvtrim_profile_begin(ctx, mask)
     torch.cuda.synchronize()
     t_begin = time.perf_counter()
@@ -163,11 +194,22 @@ def main():
     t_end = time.perf_counter()
     prof = kv.kvtrim_profile_end(ctx)
     assert kv.kvtrim_poll_error(ctx) == 0, "device-side error in the timed region"
+    if args.kernel_times:
+        for name, (ms, n) in sorted(prof.items(), key=lambda kvp: -kvp[1][0]):
+            log(f"[bench]   {name:16s} {ms / n * 1e3:8.1f} us x {n}")
     ms_per_step = (t_end - t_begin) * 1e3 / K
     alg = algorithmic_bytes(w, n_cand, n_ret, args.horizon)
     alg_total = sum(alg.values())
     stage_model_bytes = None
-    if args.unfused:
+    if args.paged:
+        # no K/V moves: the step's compulsory bytes are the score (8 B), the selection (4 B score + 1 B mask)
+        # and the eviction (1 B mask + 4 B position) per candidate, and the attention's read of K, V and the
+        # position of every retained entry
+        alg = {"score": alg["score"], "select": alg["select"], "evict": 5 * n_cand,
+               "attend": alg["attend"] + 4 * n_ret}
+        alg_total = sum(alg.values())
+        dom, dom_bytes = "k_att_partial", alg["attend"]
+    elif args.unfused:
         dom, dom_bytes = "k_cmp_copy", alg["compact"]
     else:
         # The fused kernel does the work of stages 3 and 4 but reads K/V once.  Its roofline is priced on
@@ -206,7 +248,9 @@ def main():
             "workload": f"{w.name}: S{w.n_seq} L{w.n_layers} Hkv{w.n_kv_heads} Hq{w.n_q_heads} D{w.head_dim}, "
                         f"{w.prefill[0]} prefilled, B={B} ({n_cand} candidates/step, {n_ret} retained), "
                         f"score lookahead horizon {args.horizon if args.horizon > 0 else 'infinite'}",
-            "stages": ("append, score, select_global, compact, decode_attn (five C-ABI calls per step)" if args.unfused else
+            "stages": ("paged_append, paged_score, paged_select, paged_evict, paged_attn (paged layout: no K/V moved; "
+                       "five C-ABI calls per step)" if args.paged else
+                       "append, score, select_global, compact, decode_attn (five C-ABI calls per step)" if args.unfused else
                        "append, score, select_global, compact_attn (stages 3+4 fused; four C-ABI calls per step)"),
             "first_step_ms": first_ms,
         },
@@ -228,7 +272,24 @@ def main():
         from harness import attn_error, compare_caches, device_cache_to_host
         from helpers import bf16_bits
         s = W + K
-        hc = device_cache_to_host(w, state["src"])
+        if args.paged:                          # the pages as the oracle's ragged cache: each segment in position order
+            from paged_harness import PagedHost
+            ph = PagedHost(pc)
+            idx, counts = ph.ordered_slots()
+            starts = np.concatenate([[0], np.cumsum(counts.astype(np.int64) + reserve)[:-1]])
+            at = np.concatenate([st + np.arange(n) for st, n in zip(starts, counts)])
+            n_host = int(counts.sum()) + reserve * w.nseg
+
+            def spread(a):
+                o = np.zeros((n_host,) + a.shape[1:], a.dtype)
+                o[at] = a[idx]
+                return o
+            hc = oracle.HostCache.from_arrays(oracle.Shape(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim),
+                                              spread(ph.k), spread(ph.v), spread(ph.log_beta), spread(ph.pos), starts,
+                                              counts, log_tail=None if ph.log_tail is None else spread(ph.log_tail))
+            del ph
+        else:
+            hc = device_cache_to_host(w, state["src"])
         inp = {k: v.cpu() for k, v in inputs[s].items()}
         now = now0 + s + 1
         pos_new = np.repeat(now, per_seq).astype(np.int32)
@@ -243,7 +304,11 @@ def main():
         step(s)
         torch.cuda.synchronize()
         ok_sel = bool(np.array_equal(kept.cpu().numpy(), kept_ref))
-        ok_cache = compare_caches(device_cache_to_host(w, state["src"]), hc_next)
+        if args.paged:
+            ph = PagedHost(pc)
+            ok_cache = ph.structure_problems() == [] and ph.equals(hc_next)
+        else:
+            ok_cache = compare_caches(device_cache_to_host(w, state["src"]), hc_next)
         err = attn_error(out.cpu().numpy(), out_ref)
         log(f"[bench] oracle step on the host: {cpu_s:.2f} s; GPU vs oracle on that step: kept equal={ok_sel}, "
             f"cache equal={ok_cache}, attention err={err:.2e}")

@@ -94,8 +94,9 @@ struct PV<G, E, G> {
 // partial layout: [chunk][G][D + 2] = (m in base-2 units, l, o[D] unnormalised)
 // SOFT: retention-gated attention of Sec. 2.2 - the logit of entry i gets the bias (t - i) log(beta_i),
 // t = now[seq] (the weights beta^(t-i) e^z of the soft form); otherwise hard eviction, no bias.
-// PAGED: the chunk is a page of a paged cache; slots with a negative position are empty and take no
-// part (their logit is -inf and their V row, which may hold anything, is replaced by zeros).
+// PAGED: the chunk is a run of pages of a paged cache - cd.first indexes the first of them in the block
+// tables, cd.n counts their slots; slots with a negative position are empty and take no part (their
+// logit is -inf and their V row, which may hold anything, is replaced by zeros).
 template <int D, int G, bool SOFT, bool PAGED>
 __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const uint16_t* __restrict__ q,
                                                              Shape sh, Workspace ws, int chunk,
@@ -138,16 +139,33 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
     const vec* vp = reinterpret_cast<const vec*>(c.v);
     constexpr int VPR = D / E;                                    // vectors per row = 16
 
+    // PAGED: the (at most four) pages of the run, looked up once so that no load of the loop waits for them
+    int pg0 = 0, pg1 = 0, pg2 = 0, pg3 = 0;
+    if (PAGED) {
+        const int32_t* bt = ws.pg_block_table + base;
+        const int np = row_end >> 7, hi = (int)(c.cap >> 7) - 1;
+        pg0 = min(max(bt[0], 0), hi);
+        pg1 = np > 1 ? min(max(bt[1], 0), hi) : 0;
+        pg2 = np > 2 ? min(max(bt[2], 0), hi) : 0;
+        pg3 = np > 3 ? min(max(bt[3], 0), hi) : 0;
+    }
+
     for (int r0 = off + wave * 16; r0 < row_end; r0 += 64) {
         const int last = row_end - 1;
+        int64_t rbase = base;                                     // entry of row 0 in this 16-row group's numbering
+        if (PAGED) {                                              // 16 | page size: the group lies in one page
+            const int pi = r0 >> 7;
+            const int pg = pi == 0 ? pg0 : (pi == 1 ? pg1 : (pi == 2 ? pg2 : pg3));
+            rbase = (int64_t)pg * KVTRIM_PAGE_SIZE - (r0 & ~(KVTRIM_PAGE_SIZE - 1));
+        }
         // K in MFMA operand layout: lane -> row r0 + c16, vectors 4j + b4
-        const int64_t krow = base + min(r0 + c16, last);
+        const int64_t krow = rbase + min(r0 + c16, last);
         vec kf[4], vf[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) kf[j] = kp[krow * VPR + 4 * j + b4];
         // V coalesced: lane -> row r0 + 4*b4 + i, vector c16
 #pragma unroll
-        for (int i = 0; i < 4; ++i) vf[i] = vp[(base + min(r0 + 4 * b4 + i, last)) * VPR + c16];
+        for (int i = 0; i < 4; ++i) vf[i] = vp[(rbase + min(r0 + 4 * b4 + i, last)) * VPR + c16];
 
         float4v acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -158,7 +176,7 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int row = r0 + 4 * b4 + i;
-            const int64_t e = base + min(row, last);
+            const int64_t e = rbase + min(row, last);
             float zi = acc[i] * scale_log2;
             if (SOFT) zi = fmaf((float)(t_now - c.pos[e]) * c.log_beta[e], 1.4426950408889634f, zi);
             bool valid = row < row_end;
@@ -384,20 +402,22 @@ kvtrim_status launch_attn(kvtrim_ctx* ctx, const CacheView& c, const uint16_t* q
     return launch_combine(ctx, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, st);
 }
 
-// Attention over the pages listed in ws.att_desc / ws.att_chunk_prefix (built by the paged plan
-// kernel): one block per page, then the per-segment merge.
-kvtrim_status launch_attn_paged(kvtrim_ctx* ctx, const CacheView& pool, const uint16_t* q, int n_pages,
-                                int32_t layer_begin, int32_t layer_end, float scale, float* out, float* lse,
-                                hipStream_t st) {
+// Attention over the page runs listed in ws.att_desc / ws.att_chunk_prefix (built by the paged plan
+// kernel; the pages themselves are looked up in block_table): one block per run, then the
+// per-segment merge.
+kvtrim_status launch_attn_paged(kvtrim_ctx* ctx, const CacheView& pool, const int32_t* block_table, const uint16_t* q,
+                                int max_chunks, int32_t layer_begin, int32_t layer_end, float scale, float* out,
+                                float* lse, hipStream_t st) {
     const Shape& sh = ctx->shape;
-    const Workspace& ws = ctx->ws;
+    Workspace ws = ctx->ws;
+    ws.pg_block_table = block_table;
     const float scale_log2 = scale * 1.4426950408889634f;
     bool ok;
     {
         ProfScope prof(ctx, K_ATT_PARTIAL, st);
         ok = sh.head_dim == 128
-                 ? dispatch_partial<128>(sh.group, pool, q, sh, ws, KVTRIM_PAGE_SIZE, scale_log2, nullptr, true, (unsigned)n_pages, st)
-                 : dispatch_partial<64>(sh.group, pool, q, sh, ws, KVTRIM_PAGE_SIZE, scale_log2, nullptr, true, (unsigned)n_pages, st);
+                 ? dispatch_partial<128>(sh.group, pool, q, sh, ws, KVTRIM_PAGE_SIZE, scale_log2, nullptr, true, (unsigned)max_chunks, st)
+                 : dispatch_partial<64>(sh.group, pool, q, sh, ws, KVTRIM_PAGE_SIZE, scale_log2, nullptr, true, (unsigned)max_chunks, st);
     }
     if (!ok) return KVTRIM_EINVAL;
     return launch_combine(ctx, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, st);

@@ -165,13 +165,17 @@ __global__ __launch_bounds__(256) void k_pg_append(PagedView pc, const uint16_t*
 }
 
 // ---------------------------------------------------------------------------------------------
-// Score: one block per page, one thread per slot.
-__global__ __launch_bounds__(P) void k_pg_score(PagedView pc, const int32_t* __restrict__ now,
-                                                float* __restrict__ score, int segs_per_seq, int nseg) {
-    const int page = blockIdx.x;
+// Score: a block takes PG_PER_BLOCK pages, one thread per slot.
+constexpr int PG_PER_BLOCK = 8;
+constexpr int PG_THREADS = PG_PER_BLOCK * P;
+
+__global__ __launch_bounds__(PG_THREADS) void k_pg_score(PagedView pc, const int32_t* __restrict__ now,
+                                                         float* __restrict__ score, int segs_per_seq, int nseg) {
+    const int page = blockIdx.x * PG_PER_BLOCK + (threadIdx.x >> 7);
+    if (page >= pc.n_pages) return;
     const int owner = pc.page_owner[page];
     if (owner < 0 || owner >= nseg) return;
-    const int64_t e = (int64_t)page * P + threadIdx.x;
+    const int64_t e = (int64_t)page * P + (threadIdx.x & (P - 1));
     const int ps = pc.pos[e];
     if (ps < 0) return;
     const float elapsed = (float)(now[owner / segs_per_seq] + 1 - ps);
@@ -179,14 +183,21 @@ __global__ __launch_bounds__(P) void k_pg_score(PagedView pc, const int32_t* __r
 }
 
 // ---------------------------------------------------------------------------------------------
-// Chunk table of a paged cache, built by ONE block: one chunk per page of the segments with
-// in_range(g), in segment order.  prefix[g] = first chunk of segment g, prefix[nseg] = number of
-// chunks; entry_prefix (optional) counts the live entries of the segments before g.  Returns the
-// number of chunks; tables that do not fit (page ids, counts) raise ERR_LAYOUT and leave it empty.
-template <typename InRange>
+// Chunk table of a paged cache: the pages of every segment with in_range(g), in segment order,
+// GROUP pages to a chunk.  prefix[g] = first chunk of segment g, prefix[nseg] = number of chunks;
+// entry_prefix (optional) counts the live entries of the segments before g.
+//   GROUP == 1: desc = {first slot of the page, page size, segment}           (selection)
+//   GROUP  > 1: desc = {index of the group's first block-table entry, slots of the group, segment}
+//               - the reader looks the pages up itself                        (attention)
+// Built by `nparts` blocks: every block scans the per-segment counts (a few thousand integers),
+// block `part` fills the descriptors of the segments g = part (mod nparts), one wavefront per
+// segment, and block 0 writes the prefixes.  Returns the number of chunks.  Counts that do not
+// fit raise ERR_LAYOUT and leave the table empty; a page id out of range raises it too and is
+// clamped, so that no reader leaves the pool.
+template <int GROUP, typename InRange>
 __device__ __forceinline__ int build_page_table(const PagedView& pc, int nseg, InRange in_range, int32_t* prefix,
                                                 ChunkDesc* desc, int64_t max_chunks, int64_t* entry_prefix,
-                                                int32_t* err) {
+                                                int32_t* err, int part, int nparts) {
     __shared__ uint64_t s_scan[17];
     __shared__ int s_bad;
     __shared__ int s_c0[1024], s_n[1024];
@@ -197,53 +208,71 @@ __device__ __forceinline__ int build_page_table(const PagedView& pc, int nseg, I
     for (int base = 0; base < nseg; base += blockDim.x) {
         const int g = base + tid;
         uint64_t v = 0;
+        int npg = 0;
         if (g < nseg) {
-            const int npg = pc.seg_pages[g], live = pc.seg_live[g];
-            if (npg < 0 || npg > pc.max_pps || live < 0 || (int64_t)live > (int64_t)npg * P) s_bad = 1;
-            else if (in_range(g)) v = ((uint64_t)live << 32) | (uint64_t)npg;
+            npg = pc.seg_pages[g];
+            const int live = pc.seg_live[g];
+            if (npg < 0 || npg > pc.max_pps || live < 0 || (int64_t)live > (int64_t)npg * P) {
+                s_bad = 1;
+                npg = 0;
+            } else if (in_range(g)) {
+                v = ((uint64_t)live << 32) | (uint64_t)((npg + GROUP - 1) / GROUP);
+            } else {
+                npg = 0;
+            }
         }
         uint64_t tot;
         const uint64_t ex = carry + block_excl_scan<uint64_t>(v, s_scan, &tot);
         carry += tot;
-        const int c0 = (int)(ex & 0xffffffffu), n = (int)(v & 0xffffffffu);
-        if (g < nseg) {
+        const int c0 = (int)(ex & 0xffffffffu);
+        if (g < nseg && part == 0) {
             prefix[g] = c0;
             if (entry_prefix) entry_prefix[g] = (int64_t)(ex >> 32);
         }
         s_c0[tid] = c0;
-        s_n[tid] = n;
+        s_n[tid] = npg;
         __syncthreads();
-        const bool fits = !s_bad && (int64_t)(carry & 0xffffffffu) <= max_chunks;
-        if (fits) {                                                  // one wavefront per segment of the tile
+        if (!s_bad && (int64_t)(carry & 0xffffffffu) <= max_chunks) {
             const int lane = lane_id(), wave = tid >> 6, nw = blockDim.x >> 6;
             const int ntile = min((int)blockDim.x, nseg - base);
-            for (int t = wave; t < ntile; t += nw) {
+            const int first_t = ((part - base) % nparts + nparts) % nparts;      // first t with (base + t) = part (mod nparts)
+            for (int t = first_t + wave * nparts; t < ntile; t += nw * nparts) {
                 const int gg = base + t, cc = s_c0[t], nn = s_n[t];
-                const int32_t* bt = pc.block_table + (int64_t)gg * pc.max_pps;
+                const int64_t row = (int64_t)gg * pc.max_pps;
+                bool bad_page = false;
                 for (int i = lane; i < nn; i += 64) {
-                    const int pg = bt[i];
-                    if (pg < 0 || pg >= pc.n_pages) s_bad = 1;
+                    const int pg = pc.block_table[row + i];
+                    bad_page |= pg < 0 || pg >= pc.n_pages;
                     ChunkDesc d;
-                    d.first = (int64_t)max(pg, 0) * P;
-                    d.n = P;
                     d.seg = gg;
-                    desc[cc + i] = d;
+                    if (GROUP == 1) {
+                        d.first = (int64_t)min(max(pg, 0), pc.n_pages - 1) * P;
+                        d.n = P;
+                        desc[cc + i] = d;
+                    } else if (i % GROUP == 0) {
+                        d.first = row + i;
+                        d.n = P * min(GROUP, nn - i);
+                        desc[cc + i / GROUP] = d;
+                    }
                 }
+                if (__any(bad_page) && lane == 0) atomicOr(err, ERR_LAYOUT);
             }
         }
         __syncthreads();
     }
     const int64_t total = (int64_t)(carry & 0xffffffffu);
     if (s_bad || total > max_chunks) {
-        if (tid == 0) atomicOr(err, ERR_LAYOUT);
-        for (int g = tid; g <= nseg; g += blockDim.x) {
-            prefix[g] = 0;
-            if (entry_prefix) entry_prefix[g] = 0;
+        if (part == 0) {
+            if (tid == 0) atomicOr(err, ERR_LAYOUT);
+            for (int g = tid; g <= nseg; g += blockDim.x) {
+                prefix[g] = 0;
+                if (entry_prefix) entry_prefix[g] = 0;
+            }
         }
         __syncthreads();
         return 0;
     }
-    if (tid == 0) {
+    if (tid == 0 && part == 0) {
         prefix[nseg] = (int32_t)total;
         if (entry_prefix) entry_prefix[nseg] = (int64_t)(carry >> 32);
     }
@@ -251,37 +280,54 @@ __device__ __forceinline__ int build_page_table(const PagedView& pc, int nseg, I
     return (int)total;
 }
 
+constexpr int PG_TABLE_BLOCKS = 16;
 constexpr int PG_PLAN_ZERO_BLOCKS = 8;
+constexpr int ATT_PAGE_GROUP = 4;          // pages per attention chunk (512 rows, the ragged path's chunk)
 
-// Plan of the paged selection: block 0 builds the chunk table (in the compaction's table slots of
-// the workspace, which a paged step does not otherwise use), the chunk range of every histogram
-// block and the per-sequence state; the other blocks clear the histograms.
+// segment that owns chunk c: the last g with prefix[g] <= c (prefix[nseg] > c)
+__device__ __forceinline__ int seg_of_chunk(const int32_t* prefix, int nseg, int c) {
+    int lo = 0, hi = nseg;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (prefix[mid] > c) hi = mid;
+        else lo = mid + 1;
+    }
+    return lo - 1;
+}
+
+// Plan of the paged selection: blocks [0, PG_TABLE_BLOCKS) build the chunk table (in the
+// compaction's table slots of the workspace, which a paged step does not otherwise use); block 0
+// also sets the chunk range of every histogram block and the per-sequence state; the remaining
+// blocks clear the histograms.
 __global__ __launch_bounds__(1024) void k_pg_plan(PagedView pc, Shape sh, const int64_t* __restrict__ budget,
                                                   Workspace ws, int32_t* __restrict__ kept_out,
                                                   uint32_t* __restrict__ thr_out, int hist_blocks) {
-    if (blockIdx.x > 0) {
+    if (blockIdx.x >= PG_TABLE_BLOCKS) {
         const int n = 3 * HIST_REPLICAS * sh.n_seq * RADIX_BINS;
-        for (int i = (blockIdx.x - 1) * blockDim.x + threadIdx.x; i < n; i += (gridDim.x - 1) * blockDim.x)
-            ws.hist[i] = 0;
+        const int zb = blockIdx.x - PG_TABLE_BLOCKS, nzb = gridDim.x - PG_TABLE_BLOCKS;
+        for (int i = zb * blockDim.x + threadIdx.x; i < n; i += nzb * blockDim.x) ws.hist[i] = 0;
         return;
     }
     const int tid = threadIdx.x;
-    for (int i = tid; i < DONE_WORDS; i += blockDim.x) ws.done[i] = 0;
-    for (int g = tid; g < sh.nseg; g += blockDim.x) {
-        kept_out[g] = 0;
-        ws.tie_cnt[g] = 0;
-        ws.tie_mode[g] = 0;
-        ws.tie_thr[g] = 0;
+    if (blockIdx.x == 0) {
+        for (int i = tid; i < DONE_WORDS; i += blockDim.x) ws.done[i] = 0;
+        for (int g = tid; g < sh.nseg; g += blockDim.x) {
+            kept_out[g] = 0;
+            ws.tie_cnt[g] = 0;
+            ws.tie_mode[g] = 0;
+            ws.tie_thr[g] = 0;
+        }
     }
-    const int total = build_page_table(pc, sh.nseg, [](int) { return true; }, ws.cmp_chunk_prefix, ws.cmp_desc,
-                                       ws.max_cmp_chunks, ws.sel_entry_prefix, ws.err);
+    const int total = build_page_table<1>(pc, sh.nseg, [](int) { return true; }, ws.cmp_chunk_prefix, ws.cmp_desc,
+                                          ws.max_cmp_chunks, ws.sel_entry_prefix, ws.err, blockIdx.x, PG_TABLE_BLOCKS);
+    if (blockIdx.x != 0) return;
     if (tid < hist_blocks) {
         const int cpb = (total + hist_blocks - 1) / hist_blocks;
         const int c0 = min(total, tid * cpb), c1 = min(total, c0 + cpb);
         int4 r = make_int4(c0, c1, 0, -1);
         if (c0 < c1) {
-            r.z = ws.cmp_desc[c0].seg / sh.segs_per_seq;
-            r.w = ws.cmp_desc[c1 - 1].seg / sh.segs_per_seq;
+            r.z = seg_of_chunk(ws.cmp_chunk_prefix, sh.nseg, c0) / sh.segs_per_seq;
+            r.w = seg_of_chunk(ws.cmp_chunk_prefix, sh.nseg, c1 - 1) / sh.segs_per_seq;
         }
         ws.sel_blk[tid] = r;
     }
@@ -310,7 +356,57 @@ __global__ __launch_bounds__(1024) void k_pg_att_plan(PagedView pc, Shape sh, Wo
         const int layer = (g / H) % L;
         return layer >= layer_begin && layer < layer_end;
     };
-    build_page_table(pc, sh.nseg, in_range, ws.att_chunk_prefix, ws.att_desc, ws.max_att_chunks, nullptr, ws.err);
+    build_page_table<ATT_PAGE_GROUP>(pc, sh.nseg, in_range, ws.att_chunk_prefix, ws.att_desc, ws.max_att_chunks, nullptr,
+                                     ws.err, blockIdx.x, gridDim.x);
+}
+
+// Mask of the paged selection: a block takes PG_PER_BLOCK pages, one thread per slot.  The
+// survivors are credited to their segment with one device-scope atomic per run of wavefronts of
+// the same segment (a block mostly holds pages of one segment): atomics that meet on one cache
+// line are served one after the other, and one per wavefront made this kernel ten times slower.
+__global__ __launch_bounds__(PG_THREADS) void k_pg_mask(PagedView pc, const float* __restrict__ score, Shape sh,
+                                                        Workspace ws, uint8_t* __restrict__ keep,
+                                                        int32_t* __restrict__ kept_out) {
+    constexpr int NW = PG_THREADS / 64;
+    __shared__ int s_n[NW], s_seg[NW];
+    const int total = ws.cmp_chunk_prefix[sh.nseg];
+    const int ch = blockIdx.x * PG_PER_BLOCK + (threadIdx.x >> 7);
+    int n = 0, seg = -1;
+    if (ch < total) {                                                // uniform over the wavefront
+        const ChunkDesc d = ws.cmp_desc[ch];
+        const SelState st = ws.sel[d.seg / sh.segs_per_seq];
+        const int64_t e = d.first + (threadIdx.x & (P - 1));
+        const int ps = pc.pos[e];
+        bool k = false;
+        if (ps >= 0 && !st.keep_none) {
+            const uint32_t key = key_of_score(score[e]);
+            if (!st.need_rank) {
+                k = key >= st.thr_key;
+            } else {
+                const int mode = ws.tie_mode[d.seg];                 // 0: no tie survives, 1: all, 2: positions <= tie_thr
+                k = key > st.thr_key || (key == st.thr_key && (mode == 1 || (mode == 2 && ps <= ws.tie_thr[d.seg])));
+            }
+        }
+        keep[e] = k;
+        if (!st.need_rank) {                                         // otherwise the count kernel has credited the segments
+            n = __popcll(__ballot(k));
+            seg = d.seg;
+        }
+    }
+    const int wave = threadIdx.x >> 6;
+    if (lane_id() == 0) {
+        s_n[wave] = n;
+        s_seg[wave] = seg;
+    }
+    __syncthreads();
+    if (threadIdx.x < NW) {
+        const int w = threadIdx.x, sg = s_seg[w];
+        if (sg >= 0 && (w == 0 || s_seg[w - 1] != sg)) {             // first wavefront of a run
+            int sum = 0;
+            for (int j = w; j < NW && s_seg[j] == sg; ++j) sum += s_n[j];
+            if (sum) atomicAdd(&kept_out[sg], sum);
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -319,41 +415,39 @@ __global__ __launch_bounds__(1024) void k_pg_att_plan(PagedView pc, Shape sh, Wo
 // quota of every sequence into a rule per segment - in (layer, head) order the ties of a segment
 // all survive, or none does, and in at most one segment only the q ties with the smallest
 // positions survive; that position bound is found by a radix select over the segment's ties.
-constexpr int PGC_THREADS = 1024;
-
 __device__ __forceinline__ bool is_tie(const PagedView& pc, const float* score, int64_t e, uint32_t thr, int* pos_out) {
     const int ps = pc.pos[e];
     *pos_out = ps;
     return ps >= 0 && key_of_score(score[e]) == thr;
 }
 
+constexpr int PGC_THREADS = 256;           // two pages per block and sweep
+constexpr int PGC_BINS_PER_THREAD = 2048 / PGC_THREADS;
+
 __global__ __launch_bounds__(PGC_THREADS) void k_pg_count(PagedView pc, const float* __restrict__ score, Shape sh,
                                                           Workspace ws, int32_t* __restrict__ kept_out) {
+    if (ws.done[127] == 0) return;                                   // uniform over the grid: every tie fits
     __shared__ int64_t lds64[17];
     __shared__ int32_t lds32[17];
     __shared__ uint32_t h[2048];
     __shared__ int is_last, s_part_seg, s_part_q, s_digit, s_rank;
-    if (ws.done[127] == 0) return;                                   // uniform over the grid
     const int tid = threadIdx.x;
     const int total = ws.cmp_chunk_prefix[sh.nseg];
-    for (int ch = blockIdx.x; ch < total; ch += gridDim.x) {
+    for (int ch = blockIdx.x * 2 + (tid >> 7); ch < total; ch += gridDim.x * 2) {
         const ChunkDesc d = ws.cmp_desc[ch];
         const SelState st = ws.sel[d.seg / sh.segs_per_seq];
-        if (!st.need_rank) continue;                                 // uniform over the block
-        int gt = 0, eq = 0;
-        if (tid < P) {
-            const int64_t e = d.first + tid;
-            if (pc.pos[e] >= 0) {
-                const uint32_t key = key_of_score(score[e]);
-                gt = key > st.thr_key;
-                eq = key == st.thr_key;
-            }
+        if (!st.need_rank) continue;                                 // uniform over the wavefront
+        const int64_t e = d.first + (tid & (P - 1));
+        bool gt = false, eq = false;
+        if (pc.pos[e] >= 0) {
+            const uint32_t key = key_of_score(score[e]);
+            gt = key > st.thr_key;
+            eq = key == st.thr_key;
         }
-        gt = block_sum<int32_t>(gt, lds32);
-        eq = block_sum<int32_t>(eq, lds32);
-        if (tid == 0) {
-            if (gt) atomicAdd(&kept_out[d.seg], gt);
-            if (eq) atomicAdd(&ws.tie_cnt[d.seg], eq);
+        const int ngt = __popcll(__ballot(gt)), neq = __popcll(__ballot(eq));
+        if (lane_id() == 0) {
+            if (ngt) atomicAdd(&kept_out[d.seg], ngt);
+            if (neq) atomicAdd(&ws.tie_cnt[d.seg], neq);
         }
     }
     __syncthreads();
@@ -401,7 +495,8 @@ __global__ __launch_bounds__(PGC_THREADS) void k_pg_count(PagedView pc, const fl
             for (int i = tid; i < 2048; i += PGC_THREADS) h[i] = 0;
             __syncthreads();
             for (int64_t s = tid; s < (int64_t)npg * P; s += PGC_THREADS) {
-                const int64_t e = (int64_t)bt[s / P] * P + (s % P);
+                const int pg = min(max(bt[s / P], 0), pc.n_pages - 1);
+                const int64_t e = (int64_t)pg * P + (s % P);
                 int ps;
                 if (is_tie(pc, score, e, st.thr_key, &ps)) {
                     const uint32_t up = (uint32_t)ps;
@@ -410,19 +505,24 @@ __global__ __launch_bounds__(PGC_THREADS) void k_pg_count(PagedView pc, const fl
                 }
             }
             __syncthreads();
-            // ascending walk: thread t owns bins 2t, 2t+1
-            const uint32_t c0 = h[2 * tid], c1 = h[2 * tid + 1];
+            // ascending walk: thread t owns bins [t * PGC_BINS_PER_THREAD, (t + 1) * PGC_BINS_PER_THREAD)
+            int32_t mine = 0;
+#pragma unroll
+            for (int i = 0; i < PGC_BINS_PER_THREAD; ++i) mine += (int32_t)h[tid * PGC_BINS_PER_THREAD + i];
             int32_t tot;
-            const int32_t below = block_excl_scan<int32_t>((int32_t)(c0 + c1), lds32, &tot);
+            int32_t below = block_excl_scan<int32_t>(mine, lds32, &tot);
             const int rank = s_rank;
             __syncthreads();
-            if (below < rank && rank <= below + (int32_t)(c0 + c1)) {
-                if (rank <= below + (int32_t)c0) {
-                    s_digit = 2 * tid;
-                    s_rank = rank - below;
-                } else {
-                    s_digit = 2 * tid + 1;
-                    s_rank = rank - below - (int32_t)c0;
+            if (below < rank && rank <= below + mine) {
+#pragma unroll
+                for (int i = 0; i < PGC_BINS_PER_THREAD; ++i) {
+                    const int32_t c = (int32_t)h[tid * PGC_BINS_PER_THREAD + i];
+                    if (rank <= below + c) {
+                        s_digit = tid * PGC_BINS_PER_THREAD + i;
+                        s_rank = rank - below;
+                        break;
+                    }
+                    below += c;
                 }
             }
             __syncthreads();
@@ -438,28 +538,22 @@ __global__ __launch_bounds__(PGC_THREADS) void k_pg_count(PagedView pc, const fl
 }
 
 // ---------------------------------------------------------------------------------------------
-// Eviction: one block per page.  A page left without a live entry is marked for release
-// (owner -2); k_pg_tidy takes it out of its segment's block table and pushes it on the free list.
-__global__ __launch_bounds__(P) void k_pg_evict(PagedView pc, const uint8_t* __restrict__ keep, int nseg) {
-    __shared__ int s_cnt[P / 64];
-    const int page = blockIdx.x;
-    const int owner = pc.page_owner[page];
-    if (owner < 0 || owner >= nseg) return;                          // uniform over the block
-    const int64_t e = (int64_t)page * P + threadIdx.x;
+// Eviction: a block takes PG_PER_BLOCK pages, one thread per slot.  A page left without a live
+// entry is marked for release (owner -2); k_pg_tidy takes it out of its segment's block table
+// and pushes it on the free list.
+__global__ __launch_bounds__(PG_THREADS) void k_pg_evict(PagedView pc, const uint8_t* __restrict__ keep, int nseg) {
+    const int page = blockIdx.x * PG_PER_BLOCK + (threadIdx.x >> 7);
+    const int owner = page < pc.n_pages ? pc.page_owner[page] : -1;
+    __syncthreads();                                                 // both wavefronts of a page have read its owner
+    if (owner < 0 || owner >= nseg) return;                          // uniform over the wavefront
+    const int64_t e = (int64_t)page * P + (threadIdx.x & (P - 1));
     const bool ev = pc.pos[e] >= 0 && keep[e] == 0;
     if (ev) pc.pos[e] = -1;
-    const int c = __popcll(__ballot(ev));
-    if (lane_id() == 0) s_cnt[threadIdx.x >> 6] = c;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int n = 0;
-        for (int w = 0; w < P / 64; ++w) n += s_cnt[w];
-        if (n) {
-            const int left = pc.page_live[page] - n;
-            pc.page_live[page] = left;
-            atomicSub(&pc.seg_live[owner], n);
-            if (left <= 0) pc.page_owner[page] = -2;
-        }
+    const int n = __popcll(__ballot(ev));
+    if (n && lane_id() == 0) {
+        const int left = atomicSub(&pc.page_live[page], n) - n;
+        atomicSub(&pc.seg_live[owner], n);
+        if (left <= 0) pc.page_owner[page] = -2;
     }
 }
 
@@ -624,8 +718,8 @@ kvtrim_status kvtrim_paged_score(kvtrim_ctx* ctx, const kvtrim_paged_cache* c, c
     if (!now || !score_out) return bad(ctx, "now / score_out is NULL");
     hipStream_t st = (hipStream_t)hip_stream;
     ProfScope prof(ctx, K_PG_SCORE, st);
-    hipLaunchKernelGGL(k_pg_score, dim3(c->n_pages), dim3(P), 0, st, view_of(c), now, score_out, ctx->shape.segs_per_seq,
-                       ctx->shape.nseg);
+    hipLaunchKernelGGL(k_pg_score, dim3((c->n_pages + PG_PER_BLOCK - 1) / PG_PER_BLOCK), dim3(PG_THREADS), 0, st, view_of(c),
+                       now, score_out, ctx->shape.segs_per_seq, ctx->shape.nseg);
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;
 }
@@ -640,7 +734,7 @@ kvtrim_status kvtrim_paged_select(kvtrim_ctx* ctx, const kvtrim_paged_cache* c, 
     const int hist_blocks = c->n_pages < HIST_BLOCKS_MAX ? c->n_pages : HIST_BLOCKS_MAX;
     {
         ProfScope prof(ctx, K_PG_PLAN, st);
-        hipLaunchKernelGGL(k_pg_plan, dim3(1 + PG_PLAN_ZERO_BLOCKS), dim3(1024), 0, st, pv, ctx->shape, budget, ctx->ws,
+        hipLaunchKernelGGL(k_pg_plan, dim3(PG_TABLE_BLOCKS + PG_PLAN_ZERO_BLOCKS), dim3(1024), 0, st, pv, ctx->shape, budget, ctx->ws,
                            kept_out, thr_key_out, hist_blocks);
     }
     SelTables tb;
@@ -650,10 +744,15 @@ kvtrim_status kvtrim_paged_select(kvtrim_ctx* ctx, const kvtrim_paged_cache* c, 
     for (int pass = 0; pass < 3; ++pass) launch_select_passes_paged(ctx, score, tb, hist_blocks, pass, thr_key_out, st);
     {
         ProfScope prof(ctx, K_PG_COUNT, st);
-        hipLaunchKernelGGL(k_pg_count, dim3(c->n_pages < 256 ? c->n_pages : 256), dim3(PGC_THREADS), 0, st, pv, score,
-                           ctx->shape, ctx->ws, kept_out);
+        const int pairs = (c->n_pages + 1) / 2;
+        hipLaunchKernelGGL(k_pg_count, dim3(pairs < 128 ? pairs : 128), dim3(PGC_THREADS), 0, st, pv, score, ctx->shape,
+                           ctx->ws, kept_out);
     }
-    launch_select_mask_paged(ctx, score, tb, c->n_pages, keep_out, kept_out, st);
+    {
+        ProfScope prof(ctx, K_SEL_MASK, st);
+        hipLaunchKernelGGL(k_pg_mask, dim3((c->n_pages + PG_PER_BLOCK - 1) / PG_PER_BLOCK), dim3(PG_THREADS), 0, st, pv, score,
+                           ctx->shape, ctx->ws, keep_out, kept_out);
+    }
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;
 }
@@ -666,7 +765,8 @@ kvtrim_status kvtrim_paged_evict(kvtrim_ctx* ctx, kvtrim_paged_cache* c, const u
     const PagedView pv = view_of(c);
     {
         ProfScope prof(ctx, K_PG_EVICT, st);
-        hipLaunchKernelGGL(k_pg_evict, dim3(c->n_pages), dim3(P), 0, st, pv, keep, ctx->shape.nseg);
+        hipLaunchKernelGGL(k_pg_evict, dim3((c->n_pages + PG_PER_BLOCK - 1) / PG_PER_BLOCK), dim3(PG_THREADS), 0, st, pv, keep,
+                           ctx->shape.nseg);
     }
     {
         ProfScope prof(ctx, K_PG_TIDY, st);
@@ -685,14 +785,17 @@ kvtrim_status kvtrim_paged_attn(kvtrim_ctx* ctx, const kvtrim_paged_cache* c, co
     if (layer_begin < 0 || layer_end > ctx->cfg.n_layers || layer_begin >= layer_end)
         return bad(ctx, "empty or out-of-range layer range");
     if (!(softmax_scale == softmax_scale)) return bad(ctx, "softmax_scale is NaN");
-    if (c->n_pages > ctx->ws.max_att_chunks) return bad(ctx, "too many pages for the partial-result buffer of this context");
+    if ((int64_t)c->n_pages / ATT_PAGE_GROUP + ctx->shape.nseg > ctx->ws.max_att_chunks)
+        return bad(ctx, "too many pages for the partial-result buffer of this context");
     hipStream_t st = (hipStream_t)hip_stream;
     {
         ProfScope prof(ctx, K_PG_ATT_PLAN, st);
-        hipLaunchKernelGGL(k_pg_att_plan, dim3(1), dim3(1024), 0, st, view_of(c), ctx->shape, ctx->ws, layer_begin, layer_end);
+        hipLaunchKernelGGL(k_pg_att_plan, dim3(PG_TABLE_BLOCKS), dim3(1024), 0, st, view_of(c), ctx->shape, ctx->ws,
+                           layer_begin, layer_end);
     }
-    return launch_attn_paged(ctx, pool_view(c), (const uint16_t*)q, c->n_pages, layer_begin, layer_end, softmax_scale, out,
-                             lse, st);
+    const int max_chunks = c->n_pages / ATT_PAGE_GROUP + ctx->shape.nseg;   // sum over segments of ceil(pages / group)
+    return launch_attn_paged(ctx, pool_view(c), c->block_table, (const uint16_t*)q, max_chunks, layer_begin, layer_end,
+                             softmax_scale, out, lse, st);
 }
 
 }  // extern "C"

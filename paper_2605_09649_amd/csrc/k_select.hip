@@ -102,9 +102,11 @@ __global__ __launch_bounds__(HIST_THREADS) void k_sel_hist(const float* __restri
                 for (int slot = tid; slot < (nt << SHIFT); slot += HIST_THREADS) {
                     const ChunkDesc d = s_desc[slot >> SHIFT];
                     const int j = slot & ((1 << SHIFT) - 1);
-                    if (j < d.n && (!PAGED || tb.pos[d.first + j] >= 0)) {
+                    if (j < d.n) {                                // the position is looked at only where the prefix matches
                         int bin;
-                        if (digit_of<PASS>(key_of_score(score[d.first + j]), prefix, &bin)) atomicAdd(&h[bin], 1u);
+                        if (digit_of<PASS>(key_of_score(score[d.first + j]), prefix, &bin) &&
+                            (!PAGED || tb.pos[d.first + j] >= 0))
+                            atomicAdd(&h[bin], 1u);
                     }
                 }
             }
@@ -236,10 +238,8 @@ __global__ __launch_bounds__(CNT_THREADS) void k_sel_count(const float* __restri
 // keep[e] = key > thr, or key == thr and the entry is among the first `quota` ties of its
 // sequence in (segment, position) order.  When every tie fits (the usual case) the kernel also
 // counts the survivors of its chunk into kept_out; otherwise the count kernel has done that.
-// Ragged caches store a segment in position order, so the ties are ranked by storage order
-// (exclusive tie counts per chunk); a paged cache stores them in any order, so the count kernel
-// has turned the quota into a rule per segment: all ties, none, or those up to a position.
-template <int SHIFT, bool PAGED>
+// A segment is stored in position order, so the ties are ranked by storage order (exclusive tie
+// counts per chunk).
 __global__ __launch_bounds__(SEL_THREADS) void k_sel_mask(const float* __restrict__ score, Shape sh,
                                                           Workspace ws, SelTables tb, uint8_t* __restrict__ keep,
                                                           int32_t* __restrict__ kept_out) {
@@ -252,7 +252,6 @@ __global__ __launch_bounds__(SEL_THREADS) void k_sel_mask(const float* __restric
     const SelState st = ws.sel[d.seg / sh.segs_per_seq];
     const float* s = score + d.first;
     uint8_t* kp = keep + d.first;
-    const int32_t* ps = PAGED ? tb.pos + d.first : nullptr;
     if (st.keep_none) {
         for (int j = tid; j < d.n; j += SEL_THREADS) kp[j] = 0;
         return;
@@ -261,22 +260,12 @@ __global__ __launch_bounds__(SEL_THREADS) void k_sel_mask(const float* __restric
         int n = 0;
 #pragma unroll 8
         for (int j = tid; j < d.n; j += SEL_THREADS) {
-            const bool k = key_of_score(s[j]) >= st.thr_key && (!PAGED || ps[j] >= 0);
+            const bool k = key_of_score(s[j]) >= st.thr_key;
             kp[j] = k;
             n += k;
         }
         n = block_sum<int32_t>(n, lds32);
         if (tid == 0 && n) atomicAdd(&kept_out[d.seg], n);
-        return;
-    }
-    if (PAGED) {
-        const int mode = ws.tie_mode[d.seg];                      // 0: no tie survives, 1: all, 2: positions <= tie_thr
-        const int pthr = ws.tie_thr[d.seg];
-        for (int j = tid; j < d.n; j += SEL_THREADS) {
-            const uint32_t key = key_of_score(s[j]);
-            const int p = ps[j];
-            kp[j] = p >= 0 && (key > st.thr_key || (key == st.thr_key && (mode == 1 || (mode == 2 && p <= pthr))));
-        }
         return;
     }
     const int64_t tbase = ws.chunk_tie_base[ch];
@@ -306,8 +295,8 @@ __global__ __launch_bounds__(SEL_THREADS) void k_sel_mask(const float* __restric
     }
 }
 
-// The three histogram passes and the mask over a paged cache whose chunk table (one chunk per
-// page) is in tb; the plan and the tie count of the paged layout live in k_paged.hip.
+// The three histogram passes over a paged cache whose chunk table (one chunk per page) is in tb;
+// the plan, the tie count and the mask of the paged layout live in k_paged.hip.
 void launch_select_passes_paged(kvtrim_ctx* ctx, const float* score, const SelTables& tb, int hist_blocks,
                                 int pass, uint32_t* thr, hipStream_t st) {
     const Shape& sh = ctx->shape;
@@ -322,13 +311,6 @@ void launch_select_passes_paged(kvtrim_ctx* ctx, const float* score, const SelTa
         ProfScope prof(ctx, K_SEL_HIST2, st);
         hipLaunchKernelGGL((k_sel_hist<2, 7, true>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr);
     }
-}
-
-void launch_select_mask_paged(kvtrim_ctx* ctx, const float* score, const SelTables& tb, int n_pages,
-                              uint8_t* keep, int32_t* kept, hipStream_t st) {
-    ProfScope prof(ctx, K_SEL_MASK, st);
-    hipLaunchKernelGGL((k_sel_mask<7, true>), dim3(n_pages), dim3(SEL_THREADS), 0, st, score, ctx->shape, ctx->ws, tb,
-                       keep, kept);
 }
 
 kvtrim_status launch_select(kvtrim_ctx* ctx, const CacheView& c, const float* score, const int64_t* budget,
@@ -353,7 +335,7 @@ kvtrim_status launch_select(kvtrim_ctx* ctx, const CacheView& c, const float* sc
     { ProfScope prof(ctx, K_SEL_COUNT, st);
       hipLaunchKernelGGL(k_sel_count, dim3(n_chunk_blocks < 256 ? n_chunk_blocks : 256), dim3(CNT_THREADS), 0, st, score, sh, ws, tb, kept); }
     { ProfScope prof(ctx, K_SEL_MASK, st);
-      hipLaunchKernelGGL((k_sel_mask<SEL_SHIFT, false>), dim3(n_chunk_blocks), dim3(SEL_THREADS), 0, st, score, sh, ws, tb, keep, kept); }
+      hipLaunchKernelGGL(k_sel_mask, dim3(n_chunk_blocks), dim3(SEL_THREADS), 0, st, score, sh, ws, tb, keep, kept); }
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;
 }

@@ -181,6 +181,7 @@ kvtrim_status kvtrim_create(kvtrim_ctx** out, const kvtrim_config* cfg) {
     w.att_chunk_prefix = (int32_t*)(b + l.off[10]);
     w.att_desc = (ChunkDesc*)(b + l.off[11]);
     w.att_partial = (float*)(b + l.off[12]);
+    w.pg_block_table = nullptr;
     w.err = (int32_t*)(b + l.off[13]);
     w.sel_entry_prefix = (int64_t*)(b + l.off[14]);
     w.sel_blk = (int4*)(b + l.off[15]);

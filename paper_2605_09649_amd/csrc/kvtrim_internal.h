@@ -103,6 +103,7 @@ struct Workspace {
     int32_t* att_chunk_prefix;   // [nseg+1]
     ChunkDesc* att_desc;         // [max_att_chunks]
     float* att_partial;          // [max_att_chunks][G][D+2]  (m, l, o[D]) per query head
+    const int32_t* pg_block_table; // paged attention only: the caller's block tables (set per launch)
     int32_t* err;                // sticky device flag
     int64_t max_sel_chunks, max_cmp_chunks, max_att_chunks;
 };
@@ -149,9 +150,8 @@ kvtrim_status launch_attn(kvtrim_ctx*, const CacheView&, const uint16_t* q, cons
                           int32_t layer_begin, int32_t layer_end, float scale, float* out, float* lse, hipStream_t);
 void launch_select_passes_paged(kvtrim_ctx*, const float* score, const SelTables&, int hist_blocks, int pass,
                                 uint32_t* thr, hipStream_t);
-void launch_select_mask_paged(kvtrim_ctx*, const float* score, const SelTables&, int n_pages, uint8_t* keep,
-                              int32_t* kept, hipStream_t);
-kvtrim_status launch_attn_paged(kvtrim_ctx*, const CacheView& pool, const uint16_t* q, int n_pages,
+kvtrim_status launch_attn_paged(kvtrim_ctx*, const CacheView& pool, const int32_t* block_table, const uint16_t* q,
+                                int max_chunks,
                                 int32_t layer_begin, int32_t layer_end, float scale, float* out, float* lse,
                                 hipStream_t);
 void launch_cmp_scan_aligned(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const int32_t* kept,
