@@ -265,6 +265,11 @@ def main():
                      "second_kernel": second},
     }
 
+    if args.paged:
+        result["config"]["pages"] = {"page_size": kv.PAGE_SIZE, "n_pages": pc.n_pages,
+                                     "in_use_after_timed_region": int(pc.seg_pages.sum().item())}
+        log(f"[bench] pages in use after the timed region: {result['config']['pages']['in_use_after_timed_region']} of {pc.n_pages}")
+
     # ---- CPU baseline: the oracle replays ONE more step of the same workload on the host cores, and the
     # GPU's result of that step is checked against it (selection/compaction bit-exact, attention 5e-3)
     if not args.no_cpu_baseline:

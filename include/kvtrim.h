@@ -205,10 +205,12 @@ kvtrim_status kvtrim_append(kvtrim_ctx *ctx, kvtrim_cache *c, const void *k_new,
  *   page_owner   int32 [n_pages]   owning segment, negative = free
  *   page_live    int32 [n_pages]   live entries in the page
  *   free_list    int32 [n_pages]   stack of free page ids; n_free int32 [1] its height
- * All of it is caller-owned device memory; kvtrim_paged_build initialises the bookkeeping.
+ * All of it is caller-owned device memory (k, v, log_beta, pos, log_tail and the score arrays
+ * 16-byte aligned, the keep mask 4-byte aligned); kvtrim_paged_build initialises the bookkeeping.
  * Slot s of page p is entry p*KVTRIM_PAGE_SIZE + s of the flat score / keep arrays.
  * n_pages * KVTRIM_PAGE_SIZE must not exceed the context's max_entries, and the calls that run
- * attention need n_pages <= 32768. */
+ * attention need n_pages / 4 + nseg to fit the context's partial-result buffer (always true
+ * when n_pages <= 131072). */
 #define KVTRIM_PAGE_SIZE 128
 typedef struct {
     void *k;
@@ -243,12 +245,13 @@ kvtrim_status kvtrim_paged_append(kvtrim_ctx *ctx, kvtrim_paged_cache *c, const 
                                   const float *log_beta_new, const float *log_tail_new, const int32_t *pos_new,
                                   void *hip_stream);
 
-/* Stage 1 on the paged layout: score_out fp32 [n_pages * KVTRIM_PAGE_SIZE], written for live slots. */
+/* Stage 1 on the paged layout: score_out fp32 [n_pages * KVTRIM_PAGE_SIZE]; the slots of every
+ * segment's pages are written (0 for empty slots), free pages are left alone. */
 kvtrim_status kvtrim_paged_score(kvtrim_ctx *ctx, const kvtrim_paged_cache *c, const int32_t *now,
                                  float *score_out, void *hip_stream);
 
 /* Stage 2 on the paged layout: same rule and outputs as kvtrim_select_global; keep_out uint8
- * [n_pages * KVTRIM_PAGE_SIZE] is written for live slots. */
+ * [n_pages * KVTRIM_PAGE_SIZE] is written for the slots of every segment's pages (0 for empty ones). */
 kvtrim_status kvtrim_paged_select(kvtrim_ctx *ctx, const kvtrim_paged_cache *c, const float *score,
                                   const int64_t *budget, uint8_t *keep_out, int32_t *kept_out,
                                   uint32_t *thr_key_out, void *hip_stream);

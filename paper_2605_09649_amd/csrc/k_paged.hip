@@ -165,21 +165,40 @@ __global__ __launch_bounds__(256) void k_pg_append(PagedView pc, const uint16_t*
 }
 
 // ---------------------------------------------------------------------------------------------
-// Score: a block takes PG_PER_BLOCK pages, one thread per slot.
+// Score: a block takes PG_PER_BLOCK pages; a thread takes four consecutive slots (16-byte loads
+// and stores).  Empty slots of a segment's pages get 0; free pages are skipped.
 constexpr int PG_PER_BLOCK = 8;
-constexpr int PG_THREADS = PG_PER_BLOCK * P;
+constexpr int PG_THREADS = PG_PER_BLOCK * P;         // one thread per slot (eviction)
+constexpr int PG4_THREADS = PG_PER_BLOCK * P / 4;    // one thread per four slots (score, mask)
 
-__global__ __launch_bounds__(PG_THREADS) void k_pg_score(PagedView pc, const int32_t* __restrict__ now,
-                                                         float* __restrict__ score, int segs_per_seq, int nseg) {
-    const int page = blockIdx.x * PG_PER_BLOCK + (threadIdx.x >> 7);
+__global__ __launch_bounds__(PG4_THREADS) void k_pg_score(PagedView pc, const int32_t* __restrict__ now,
+                                                          float* __restrict__ score, int segs_per_seq, int nseg) {
+    const int page = blockIdx.x * PG_PER_BLOCK + (threadIdx.x >> 5);
     if (page >= pc.n_pages) return;
     const int owner = pc.page_owner[page];
     if (owner < 0 || owner >= nseg) return;
-    const int64_t e = (int64_t)page * P + (threadIdx.x & (P - 1));
-    const int ps = pc.pos[e];
-    if (ps < 0) return;
-    const float elapsed = (float)(now[owner / segs_per_seq] + 1 - ps);
-    score[e] = pc.log_tail ? __fmaf_rn(elapsed, pc.log_beta[e], pc.log_tail[e]) : __fmul_rn(elapsed, pc.log_beta[e]);
+    const int64_t e = (int64_t)page * P + (threadIdx.x & 31) * 4;
+    const int4 ps = *reinterpret_cast<const int4*>(pc.pos + e);
+    const float4 lb = *reinterpret_cast<const float4*>(pc.log_beta + e);
+    const int t1 = now[owner / segs_per_seq] + 1;
+    float4 r;
+    if (pc.log_tail) {
+        const float4 lt = *reinterpret_cast<const float4*>(pc.log_tail + e);
+        r.x = __fmaf_rn((float)(t1 - ps.x), lb.x, lt.x);
+        r.y = __fmaf_rn((float)(t1 - ps.y), lb.y, lt.y);
+        r.z = __fmaf_rn((float)(t1 - ps.z), lb.z, lt.z);
+        r.w = __fmaf_rn((float)(t1 - ps.w), lb.w, lt.w);
+    } else {
+        r.x = __fmul_rn((float)(t1 - ps.x), lb.x);
+        r.y = __fmul_rn((float)(t1 - ps.y), lb.y);
+        r.z = __fmul_rn((float)(t1 - ps.z), lb.z);
+        r.w = __fmul_rn((float)(t1 - ps.w), lb.w);
+    }
+    if (ps.x < 0) r.x = 0.f;
+    if (ps.y < 0) r.y = 0.f;
+    if (ps.z < 0) r.z = 0.f;
+    if (ps.w < 0) r.w = 0.f;
+    *reinterpret_cast<float4*>(score + e) = r;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -360,50 +379,59 @@ __global__ __launch_bounds__(1024) void k_pg_att_plan(PagedView pc, Shape sh, Wo
                                      ws.err, blockIdx.x, gridDim.x);
 }
 
-// Mask of the paged selection: a block takes PG_PER_BLOCK pages, one thread per slot.  The
-// survivors are credited to their segment with one device-scope atomic per run of wavefronts of
-// the same segment (a block mostly holds pages of one segment): atomics that meet on one cache
-// line are served one after the other, and one per wavefront made this kernel ten times slower.
-__global__ __launch_bounds__(PG_THREADS) void k_pg_mask(PagedView pc, const float* __restrict__ score, Shape sh,
-                                                        Workspace ws, uint8_t* __restrict__ keep,
-                                                        int32_t* __restrict__ kept_out) {
-    constexpr int NW = PG_THREADS / 64;
-    __shared__ int s_n[NW], s_seg[NW];
+// Mask of the paged selection: a block takes PG_PER_BLOCK pages, a thread four consecutive slots
+// (32 lanes to a page).  The survivors are credited to their segment with one device-scope atomic
+// per run of pages of the same segment (a block mostly holds pages of one segment): atomics that
+// meet on one cache line are served one after the other, and one per wavefront made this kernel
+// ten times slower.
+__global__ __launch_bounds__(PG4_THREADS) void k_pg_mask(PagedView pc, const float* __restrict__ score, Shape sh,
+                                                         Workspace ws, uint8_t* __restrict__ keep,
+                                                         int32_t* __restrict__ kept_out) {
+    __shared__ int s_n[PG_PER_BLOCK], s_seg[PG_PER_BLOCK];
     const int total = ws.cmp_chunk_prefix[sh.nseg];
-    const int ch = blockIdx.x * PG_PER_BLOCK + (threadIdx.x >> 7);
+    const int pib = threadIdx.x >> 5;                                // page of the block
+    const int ch = blockIdx.x * PG_PER_BLOCK + pib;
     int n = 0, seg = -1;
-    if (ch < total) {                                                // uniform over the wavefront
+    if (ch < total) {
         const ChunkDesc d = ws.cmp_desc[ch];
         const SelState st = ws.sel[d.seg / sh.segs_per_seq];
-        const int64_t e = d.first + (threadIdx.x & (P - 1));
-        const int ps = pc.pos[e];
-        bool k = false;
-        if (ps >= 0 && !st.keep_none) {
-            const uint32_t key = key_of_score(score[e]);
-            if (!st.need_rank) {
-                k = key >= st.thr_key;
-            } else {
-                const int mode = ws.tie_mode[d.seg];                 // 0: no tie survives, 1: all, 2: positions <= tie_thr
-                k = key > st.thr_key || (key == st.thr_key && (mode == 1 || (mode == 2 && ps <= ws.tie_thr[d.seg])));
+        const int64_t e = d.first + (threadIdx.x & 31) * 4;
+        const int4 p4 = *reinterpret_cast<const int4*>(pc.pos + e);
+        const float4 s4 = *reinterpret_cast<const float4*>(score + e);
+        const int ps[4] = {p4.x, p4.y, p4.z, p4.w};
+        const float sc[4] = {s4.x, s4.y, s4.z, s4.w};
+        int mode = 0, pthr = 0;
+        if (st.need_rank) {                                          // 0: no tie survives, 1: all, 2: positions <= tie_thr
+            mode = ws.tie_mode[d.seg];
+            pthr = ws.tie_thr[d.seg];
+        }
+        uint32_t packed = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            bool k = false;
+            if (ps[j] >= 0 && !st.keep_none) {
+                const uint32_t key = key_of_score(sc[j]);
+                k = st.need_rank ? (key > st.thr_key || (key == st.thr_key && (mode == 1 || (mode == 2 && ps[j] <= pthr))))
+                                 : key >= st.thr_key;
             }
+            packed |= (uint32_t)k << (8 * j);
+            n += k;
         }
-        keep[e] = k;
-        if (!st.need_rank) {                                         // otherwise the count kernel has credited the segments
-            n = __popcll(__ballot(k));
-            seg = d.seg;
-        }
+        *reinterpret_cast<uint32_t*>(keep + e) = packed;
+        if (!st.need_rank) seg = d.seg;                              // otherwise the count kernel has credited the segments
     }
-    const int wave = threadIdx.x >> 6;
-    if (lane_id() == 0) {
-        s_n[wave] = n;
-        s_seg[wave] = seg;
+#pragma unroll
+    for (int dlt = 16; dlt >= 1; dlt >>= 1) n += __shfl_xor(n, dlt, 64);   // sum over the 32 lanes of the page
+    if ((threadIdx.x & 31) == 0) {
+        s_n[pib] = n;
+        s_seg[pib] = seg;
     }
     __syncthreads();
-    if (threadIdx.x < NW) {
+    if (threadIdx.x < PG_PER_BLOCK) {
         const int w = threadIdx.x, sg = s_seg[w];
-        if (sg >= 0 && (w == 0 || s_seg[w - 1] != sg)) {             // first wavefront of a run
+        if (sg >= 0 && (w == 0 || s_seg[w - 1] != sg)) {             // first page of a run
             int sum = 0;
-            for (int j = w; j < NW && s_seg[j] == sg; ++j) sum += s_n[j];
+            for (int j = w; j < PG_PER_BLOCK && s_seg[j] == sg; ++j) sum += s_n[j];
             if (sum) atomicAdd(&kept_out[sg], sum);
         }
     }
@@ -635,7 +663,8 @@ static const char* paged_problem(const kvtrim_ctx* ctx, const kvtrim_paged_cache
     if (!c->k || !c->v || !c->log_beta || !c->pos || !c->block_table || !c->seg_pages || !c->seg_live ||
         !c->page_owner || !c->page_live || !c->free_list || !c->n_free)
         return "paged cache has a NULL pointer";
-    if ((((uintptr_t)c->k) | ((uintptr_t)c->v)) & 15) return "k/v not 16-byte aligned";
+    if ((((uintptr_t)c->k) | ((uintptr_t)c->v) | ((uintptr_t)c->log_beta) | ((uintptr_t)c->pos) | ((uintptr_t)c->log_tail)) & 15)
+        return "k / v / log_beta / pos / log_tail not 16-byte aligned";
     if (c->n_pages < 1 || c->max_pages_per_seg < 1) return "n_pages / max_pages_per_seg < 1";
     if ((int64_t)c->n_pages * P > ctx->cfg.max_entries) return "n_pages * page size exceeds max_entries";
     return nullptr;
@@ -716,9 +745,10 @@ kvtrim_status kvtrim_paged_score(kvtrim_ctx* ctx, const kvtrim_paged_cache* c, c
     if (!ctx) return KVTRIM_EINVAL;
     if (const char* p = paged_problem(ctx, c)) return bad(ctx, p);
     if (!now || !score_out) return bad(ctx, "now / score_out is NULL");
+    if (((uintptr_t)score_out) & 15) return bad(ctx, "score_out not 16-byte aligned");
     hipStream_t st = (hipStream_t)hip_stream;
     ProfScope prof(ctx, K_PG_SCORE, st);
-    hipLaunchKernelGGL(k_pg_score, dim3((c->n_pages + PG_PER_BLOCK - 1) / PG_PER_BLOCK), dim3(PG_THREADS), 0, st, view_of(c),
+    hipLaunchKernelGGL(k_pg_score, dim3((c->n_pages + PG_PER_BLOCK - 1) / PG_PER_BLOCK), dim3(PG4_THREADS), 0, st, view_of(c),
                        now, score_out, ctx->shape.segs_per_seq, ctx->shape.nseg);
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;
@@ -729,6 +759,7 @@ kvtrim_status kvtrim_paged_select(kvtrim_ctx* ctx, const kvtrim_paged_cache* c, 
     if (!ctx) return KVTRIM_EINVAL;
     if (const char* p = paged_problem(ctx, c)) return bad(ctx, p);
     if (!score || !budget || !keep_out || !kept_out) return bad(ctx, "score / budget / keep_out / kept_out is NULL");
+    if ((((uintptr_t)score) & 15) || (((uintptr_t)keep_out) & 3)) return bad(ctx, "score not 16-byte or keep_out not 4-byte aligned");
     hipStream_t st = (hipStream_t)hip_stream;
     const PagedView pv = view_of(c);
     const int hist_blocks = c->n_pages < HIST_BLOCKS_MAX ? c->n_pages : HIST_BLOCKS_MAX;
@@ -745,12 +776,12 @@ kvtrim_status kvtrim_paged_select(kvtrim_ctx* ctx, const kvtrim_paged_cache* c, 
     {
         ProfScope prof(ctx, K_PG_COUNT, st);
         const int pairs = (c->n_pages + 1) / 2;
-        hipLaunchKernelGGL(k_pg_count, dim3(pairs < 128 ? pairs : 128), dim3(PGC_THREADS), 0, st, pv, score, ctx->shape,
+        hipLaunchKernelGGL(k_pg_count, dim3(pairs < 1024 ? pairs : 1024), dim3(PGC_THREADS), 0, st, pv, score, ctx->shape,
                            ctx->ws, kept_out);
     }
     {
         ProfScope prof(ctx, K_SEL_MASK, st);
-        hipLaunchKernelGGL(k_pg_mask, dim3((c->n_pages + PG_PER_BLOCK - 1) / PG_PER_BLOCK), dim3(PG_THREADS), 0, st, pv, score,
+        hipLaunchKernelGGL(k_pg_mask, dim3((c->n_pages + PG_PER_BLOCK - 1) / PG_PER_BLOCK), dim3(PG4_THREADS), 0, st, pv, score,
                            ctx->shape, ctx->ws, keep_out, kept_out);
     }
     KVTRIM_HIP(ctx, hipGetLastError());
