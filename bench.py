@@ -280,18 +280,7 @@ def main():
         if args.paged:                          # the pages as the oracle's ragged cache: each segment in position order
             from paged_harness import PagedHost
             ph = PagedHost(pc)
-            idx, counts = ph.ordered_slots()
-            starts = np.concatenate([[0], np.cumsum(counts.astype(np.int64) + reserve)[:-1]])
-            at = np.concatenate([st + np.arange(n) for st, n in zip(starts, counts)])
-            n_host = int(counts.sum()) + reserve * w.nseg
-
-            def spread(a):
-                o = np.zeros((n_host,) + a.shape[1:], a.dtype)
-                o[at] = a[idx]
-                return o
-            hc = oracle.HostCache.from_arrays(oracle.Shape(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim),
-                                              spread(ph.k), spread(ph.v), spread(ph.log_beta), spread(ph.pos), starts,
-                                              counts, log_tail=None if ph.log_tail is None else spread(ph.log_tail))
+            hc = ph.as_ragged(oracle.Shape(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim), reserve)
             del ph
         else:
             hc = device_cache_to_host(w, state["src"])

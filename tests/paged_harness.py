@@ -82,6 +82,22 @@ class PagedHost:
             counts.append(len(slots))
         return (np.concatenate(idx) if idx else np.zeros(0, np.int64)), np.array(counts, np.int32)
 
+    def as_ragged(self, shape, reserve=1):
+        """The same entries as the oracle's ragged cache: every segment in position order, each
+        followed by `reserve` free slots."""
+        idx, counts = self.ordered_slots()
+        starts = np.concatenate([[0], np.cumsum(counts.astype(np.int64) + reserve)[:-1]]).astype(np.int64)
+        at = np.concatenate([st + np.arange(n) for st, n in zip(starts, counts)]) if len(idx) else idx
+        n_host = int(counts.sum()) + reserve * self.nseg
+
+        def spread(a):
+            o = np.zeros((n_host,) + a.shape[1:], a.dtype)
+            o[at] = a[idx]
+            return o
+        return oracle.HostCache.from_arrays(shape, spread(self.k), spread(self.v), spread(self.log_beta),
+                                            spread(self.pos), starts, counts,
+                                            log_tail=None if self.log_tail is None else spread(self.log_tail))
+
     def equals(self, hc):
         """Same entries per segment as the oracle's ragged cache hc."""
         idx, counts = self.ordered_slots()

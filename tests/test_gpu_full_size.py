@@ -4,6 +4,7 @@ long (32 layers x 8 KV heads, 131072 prefilled, B = 2,097,152):
   - the first eviction (33.5 M candidates): selection compared whole against the oracle (only
     metadata is needed on the host); compaction and attention on sampled segments;
   - steady-state steps (2.1 M candidates, fused stage 3+4 path): compared whole.
+  - the same steady state on the paged layout (pages built from the first eviction): compared whole.
 llama (32768 prefilled), vlm (two sequences, G = 7) and a 16-sequence multi-turn cache: whole.
 """
 import math
@@ -17,6 +18,7 @@ import oracle
 import paper_2605_09649_amd as kv
 from harness import attn_error, compare_caches, device_cache_to_host, run_steps_both
 from helpers import bf16_bits, shape_of
+from paged_harness import PagedHost
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -160,3 +162,64 @@ def test_long_128k_first_eviction_and_steady_state():
         assert attn_error(out.cpu().numpy(), out_ref) <= ATTN_TOL
         assert np.abs(lse.cpu().numpy() - lse_ref).max() <= 2e-3
         cur, flip, hc = nxt, flip ^ 1, hc_next
+
+
+def test_long_128k_paged_steady_state():
+    # first eviction on the ragged prefill cache (checked above), survivors into pages, then the
+    # paged loop at the benchmark's size and pool, every step compared whole with the oracle
+    w = ki.workload("long")
+    sh = shape_of(w)
+    reserve = 1
+    pre = ki.prefill_cache(w, reserve=reserve, device=DEV)
+    src = kv.Cache.from_dict(pre, DEV)
+    B = w.budget[0]
+    n_pages = (B + kv.PAGE_SIZE - 1) // kv.PAGE_SIZE + 3 * w.nseg + 64
+    ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, src.cap)
+    pc = kv.PagedCache(w.nseg, w.head_dim, n_pages, n_pages, DEV)
+    score = torch.zeros(src.cap, dtype=torch.float32, device=DEV)
+    keep = torch.zeros(src.cap, dtype=torch.uint8, device=DEV)
+    kept = torch.zeros(w.nseg, dtype=torch.int32, device=DEV)
+    thr = torch.zeros(1, dtype=torch.int32, device=DEV)
+    budget = torch.tensor([B], dtype=torch.int64, device=DEV)
+    out = torch.zeros(1, w.n_layers, w.n_q_heads, w.head_dim, dtype=torch.float32, device=DEV)
+    lse = torch.zeros(1, w.n_layers, w.n_q_heads, dtype=torch.float32, device=DEV)
+    scale = 1.0 / math.sqrt(w.head_dim)
+
+    inp = ki.decode_inputs(w, 0, device=DEV)
+    now = np.array([w.prefill[0]], np.int32)
+    pos_new = np.full(w.nseg, now[0], np.int32)
+    kv.kvtrim_append(ctx, src, inp["k_new"], inp["v_new"], inp["log_beta_new"], torch.from_numpy(pos_new).to(DEV), 1)
+    kv.kvtrim_score(ctx, src, torch.from_numpy(now).to(DEV), score)
+    kv.kvtrim_select_global(ctx, src, score, budget, keep, kept, thr)
+    kv.kvtrim_paged_build(ctx, src, keep, kept, pc)
+    kv.kvtrim_paged_attn(ctx, pc, inp["q"], 0, w.n_layers, scale, out, lse)
+    assert kv.kvtrim_poll_error(ctx) == 0
+    ph = PagedHost(pc)
+    assert ph.structure_problems() == []
+    assert int(ph.seg_live.sum()) == B and np.array_equal(ph.seg_live, kept.cpu().numpy())
+    hc = ph.as_ragged(sh, reserve)
+    out_ref, lse_ref = oracle.attend(hc, bf16_bits(inp["q"]), scale)      # attention over the freshly built pages
+    assert attn_error(out.cpu().numpy(), out_ref) <= ATTN_TOL
+    del pre, src, ph
+
+    dst_cap = B + 4 * w.nseg + 8
+    for step in (1, 2, 3):
+        inp = ki.decode_inputs(w, step, device=DEV)
+        now = now + 1
+        pos_new = np.full(w.nseg, now[0], np.int32)
+        kv.kvtrim_paged_append(ctx, pc, inp["k_new"], inp["v_new"], inp["log_beta_new"], torch.from_numpy(pos_new).to(DEV))
+        kv.kvtrim_paged_score(ctx, pc, torch.from_numpy(now).to(DEV), score)
+        kv.kvtrim_paged_select(ctx, pc, score, budget, keep, kept, thr)
+        kv.kvtrim_paged_evict(ctx, pc, keep)
+        kv.kvtrim_paged_attn(ctx, pc, inp["q"], 0, w.n_layers, scale, out, lse)
+        assert kv.kvtrim_poll_error(ctx) == 0
+        oracle.append(hc, bf16_bits(inp["k_new"]), bf16_bits(inp["v_new"]), inp["log_beta_new"].cpu().numpy(), pos_new)
+        s_ref = oracle.score(hc, now)
+        k_ref, kept_r, thr_r = oracle.select(hc, s_ref, np.array([B], np.int64))
+        hc = oracle.compact(hc, k_ref, dst_cap, reserve)
+        out_ref, lse_ref = oracle.attend(hc, bf16_bits(inp["q"]), scale)
+        assert np.array_equal(kept.cpu().numpy(), kept_r) and thr.cpu().numpy().view(np.uint32)[0] == thr_r[0]
+        ph = PagedHost(pc)
+        assert ph.structure_problems() == [] and ph.equals(hc), step
+        assert attn_error(out.cpu().numpy(), out_ref) <= ATTN_TOL
+        assert np.abs(lse.cpu().numpy() - lse_ref).max() <= 2e-3
