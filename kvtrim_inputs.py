@@ -242,3 +242,26 @@ def ragged_cache(w: Workload, seg_len, reserve: int = 1, device="cpu", salt: int
     c["seg_len"].copy_(torch.tensor(seg_len, dtype=torch.int32))
     del n
     return c, torch.tensor(now, dtype=torch.int32, device=device)
+
+
+def gate_weights(n_layers: int, n_kv_heads: int, d_model: int, d_g: int = 512, d_p: int = 128, b_g: float = 3.5,
+                 z_std: float = 1.5, device="cpu", seed: int = BASE_SEED + 77):
+    """Random weights of a retention gate (Sec. 4.1; hidden width d_g = 512 as in Sec. 5.1).  No trained
+    gate is available, so the weights are drawn: W1 ~ N(0, 1/d_model), W2 ~ N(0, 1/d_g), biases N(0, 0.1),
+    and the tied readout w_g ~ N(0, s^2/d_p) with s chosen so that, for N(0,1) inputs, the gate logit has
+    roughly the spread z_std around b_g that the workloads' z distributions have.  W1, W2 are bf16,
+    the rest fp32.  Returns a dict of tensors (+ 'b_g')."""
+    g = torch.Generator(device=device).manual_seed(seed)
+    rn = lambda *shape: torch.randn(*shape, generator=g, device=device, dtype=torch.float32)
+    w1 = (rn(n_layers, d_g, d_model) / d_model ** 0.5).to(torch.bfloat16)
+    c1 = rn(n_layers, d_g) * 0.1
+    w2 = (rn(n_layers, n_kv_heads, d_p, d_g) / d_g ** 0.5).to(torch.bfloat16)
+    c2 = rn(n_layers, n_kv_heads, d_p) * 0.1
+    w_g = rn(d_p) * (z_std / 0.6) / d_p ** 0.5
+    return {"w1": w1, "c1": c1, "w2": w2, "c2": c2, "w_g": w_g, "b_g": float(b_g)}
+
+
+def gate_inputs(n_layers: int, n_tok: int, d_model: int, device="cpu", salt: int = 0):
+    """Token representations entering each transformer block, bf16 [n_layers][n_tok][d_model], N(0,1)."""
+    g = torch.Generator(device=device).manual_seed(BASE_SEED + 78 + 1000003 * int(salt))
+    return torch.randn(n_layers, n_tok, d_model, generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)

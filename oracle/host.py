@@ -204,3 +204,48 @@ def append(cache, k_new, v_new, log_beta_new, pos_new, log_tail_new=None):
                           None if log_tail_new is None else _p(log_tail_new), _p(pos_new), C.c_int32(n_new))
     if rc != 0:
         raise OverflowError("oracle append: no room in a segment")
+
+
+class _CGate(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("n_heads", C.c_int32), ("d_model", C.c_int32), ("d_g", C.c_int32),
+                ("d_p", C.c_int32), ("w1", C.c_void_p), ("c1", C.c_void_p), ("w2", C.c_void_p), ("c2", C.c_void_p),
+                ("w_g", C.c_void_p), ("b_g", C.c_float)]
+
+
+class Gate:
+    """Weights of the retention gate in host memory: w1 uint16 (bf16 bits) [L][d_g][d_model], c1 fp32 [L][d_g],
+    w2 uint16 [L][H][d_p][d_g], c2 fp32 [L][H][d_p], w_g fp32 [d_p], b_g."""
+
+    def __init__(self, w1, c1, w2, c2, w_g, b_g):
+        self.w1 = np.ascontiguousarray(w1, np.uint16)
+        self.c1 = np.ascontiguousarray(c1, np.float32)
+        self.w2 = np.ascontiguousarray(w2, np.uint16)
+        self.c2 = np.ascontiguousarray(c2, np.float32)
+        self.w_g = np.ascontiguousarray(w_g, np.float32)
+        self.b_g = float(b_g)
+        self.n_layers, self.d_g, self.d_model = self.w1.shape
+        _, self.n_heads, self.d_p, dg = self.w2.shape
+        assert self.w2.shape[0] == self.n_layers and dg == self.d_g
+        assert self.c1.shape == (self.n_layers, self.d_g) and self.c2.shape == (self.n_layers, self.n_heads, self.d_p)
+        assert self.w_g.shape == (self.d_p,)
+
+    def c(self):
+        return _CGate(self.n_layers, self.n_heads, self.d_model, self.d_g, self.d_p, _p(self.w1), _p(self.c1),
+                      _p(self.w2), _p(self.c2), _p(self.w_g), self.b_g)
+
+
+def gate_forward(gate, x, layer_begin=0, layer_end=None, horizon=None):
+    """x: uint16 (bf16 bits) [layer_end - layer_begin][n_tok][d_model].  Returns (z, log_beta, log_tail), fp64
+    [n_tok][L][H]; rows of layers outside the range are NaN; log_tail is None unless a horizon is given."""
+    layer_end = gate.n_layers if layer_end is None else layer_end
+    x = np.ascontiguousarray(x, np.uint16)
+    nl, n_tok, dm = x.shape
+    assert nl == layer_end - layer_begin and dm == gate.d_model
+    shape = (n_tok, gate.n_layers, gate.n_heads)
+    z = np.full(shape, np.nan)
+    lb = np.full(shape, np.nan)
+    lt = None if horizon is None else np.full(shape, np.nan)
+    cg = gate.c()
+    lib().kvo_gate_forward(C.byref(cg), _p(x), C.c_int32(n_tok), C.c_int32(layer_begin), C.c_int32(layer_end),
+                           C.c_int32(0 if horizon is None else horizon), _p(z), _p(lb), None if lt is None else _p(lt))
+    return z, lb, lt

@@ -28,6 +28,9 @@
  *                beta^(t-i) e^z, fp64.                               [pinned]
  *   kvo_occupancy    Sec. 4.1: expected occupancy sum of beta^(t-i). [pinned]
  *   kvo_append   bookkeeping: a new token enters every segment's list.
+ *   kvo_gate_forward  Sec. 4.1 "Weight-tied retention gates": beta = sigmoid(w_g . Proj_{l,h}(x)
+ *                + b_g) for a token entering the cache, fp64, written as the
+ *                nested sums of the definition.                      [pinned]
  *
  * Readings of points the paper leaves open (listed again in the design notes):
  *   - elapsed steps = now + 1 - pos  (the score equation, not the t-i of the
@@ -38,6 +41,13 @@
  *   - budgets are per sequence.
  *   - the appended token competes like every other entry.
  *   - an empty segment attends to nothing: output 0, lse -inf.
+ *
+ *   - the retention gate: the paper fixes Proj_{l,h} as a two-layer MLP with hidden
+ *     width d_g inside a per-block gate, and the tied readout (w_g, b_g); it does not
+ *     print the activation, the width of Proj's output or which layer is per head.
+ *     Taken here: one first layer per transformer block, shared by its heads,
+ *     u = silu(W1_l x + c1_l); a second, linear layer per (block, head),
+ *     p = W2_{l,h} u + c2_{l,h} of width d_p; z = w_g . p + b_g; beta = sigmoid(z).
  *
  * Layout of a ragged cache (same meaning as at the library boundary, but these
  * are HOST pointers):
@@ -341,6 +351,75 @@ int kvo_append(const kvo_shape *sh, kvo_cache *c, const uint16_t *k_new, const u
         c->seg_len[g] += n_new;
     }
     return 0;
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * Retention gate (Sec. 4.1, "Weight-tied retention gates"; Sec. 5.1 implementation details:
+ * a small MLP per transformer block with hidden width d_g, Proj a two-layer MLP, the final linear
+ * layer (w_g, b_g) tied across all layers and heads; Sec. 3.2: beta is computed once, when the
+ * token enters the cache).
+ *
+ * Weights (HOST pointers): w1 bf16 [L][d_g][d_model], c1 fp32 [L][d_g], w2 bf16 [L][H][d_p][d_g],
+ * c2 fp32 [L][H][d_p], w_g fp32 [d_p], b_g.  x: bf16 [layer_end - layer_begin][n_tok][d_model], the
+ * token representation that enters each block of the layer range.  Outputs, fp64, indexed
+ * [(tok * L + layer) * H + head] (for one token per sequence that is segment order); entries of
+ * layers outside the range are left alone:
+ *   z_out         the gate logit w_g . Proj(x) + b_g
+ *   log_beta_out  log sigmoid(z) = -log(1 + e^-z)
+ *   log_tail_out  (optional) log sum_{k<H} beta^k for lookahead horizon H (Eq. global_score);
+ *                 H = 0 stands for the limit, -log(1 - beta). */
+typedef struct {
+    int32_t n_layers, n_heads, d_model, d_g, d_p;
+    const uint16_t *w1;
+    const float *c1;
+    const uint16_t *w2;
+    const float *c2;
+    const float *w_g;
+    float b_g;
+} kvo_gate;
+
+void kvo_gate_forward(const kvo_gate *g, const uint16_t *x, int32_t n_tok, int32_t layer_begin, int32_t layer_end,
+                      int32_t horizon, double *z_out, double *log_beta_out, double *log_tail_out) {
+    const int L = g->n_layers, H = g->n_heads, dm = g->d_model, dg = g->d_g, dp = g->d_p;
+    double *u = (double *)malloc(sizeof(double) * (size_t)dg);
+    for (int layer = layer_begin; layer < layer_end; ++layer) {
+        for (int tok = 0; tok < n_tok; ++tok) {
+            const uint16_t *xt = x + ((size_t)(layer - layer_begin) * n_tok + tok) * dm;
+            for (int j = 0; j < dg; ++j) {                 /* first layer, shared by the heads of the block */
+                const uint16_t *row = g->w1 + ((size_t)layer * dg + j) * dm;
+                double a = (double)g->c1[(size_t)layer * dg + j];
+                for (int k = 0; k < dm; ++k) a += bf16_to_f64(row[k]) * bf16_to_f64(xt[k]);
+                u[j] = a / (1.0 + exp(-a));                /* silu */
+            }
+            for (int h = 0; h < H; ++h) {
+                double z = (double)g->b_g;
+                for (int i = 0; i < dp; ++i) {             /* Proj's second layer, then the tied readout */
+                    const uint16_t *row = g->w2 + (((size_t)layer * H + h) * dp + i) * dg;
+                    double p = (double)g->c2[((size_t)layer * H + h) * dp + i];
+                    for (int j = 0; j < dg; ++j) p += bf16_to_f64(row[j]) * u[j];
+                    z += (double)g->w_g[i] * p;
+                }
+                const size_t o = ((size_t)tok * L + layer) * H + h;
+                const double lb = z >= 0 ? -log1p(exp(-z)) : z - log1p(exp(z));
+                if (z_out) z_out[o] = z;
+                log_beta_out[o] = lb;
+                if (log_tail_out) {
+                    if (horizon <= 0) {
+                        log_tail_out[o] = -log(-expm1(lb));
+                    } else {
+                        const double beta = exp(lb);
+                        double sum = 0.0, term = 1.0;
+                        for (int k = 0; k < horizon; ++k) {
+                            sum += term;
+                            term *= beta;
+                        }
+                        log_tail_out[o] = log(sum);
+                    }
+                }
+            }
+        }
+    }
+    free(u);
 }
 
 #ifdef _OPENMP
