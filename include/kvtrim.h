@@ -264,6 +264,49 @@ kvtrim_status kvtrim_paged_evict(kvtrim_ctx *ctx, kvtrim_paged_cache *c, const u
 kvtrim_status kvtrim_paged_attn(kvtrim_ctx *ctx, const kvtrim_paged_cache *c, const void *q, int32_t layer_begin,
                                 int32_t layer_end, float softmax_scale, float *out, float *lse, void *hip_stream);
 
+/* ---- Retention gate for tokens that enter the cache (Sec. 4.1 "Weight-tied retention gates";
+ * Sec. 5.1: a small MLP per transformer block with hidden width d_g = 512, Proj a two-layer MLP,
+ * the final linear layer tied across all layers and heads; Sec. 3.2: beta is computed once, when
+ * the token is cached).  For layer l, KV head h and token representation x (the input of block l):
+ *     u = silu(W1_l x + c1_l)            first layer, one per block, width d_g
+ *     p = W2_{l,h} u + c2_{l,h}          second layer of Proj, one per (block, head), width d_p
+ *     z = w_g . p + b_g                  tied readout;  beta = sigmoid(z)
+ * (the activation, d_p and the sharing of the first layer by the heads of a block are this
+ * build's reading; the paper does not print them).
+ *
+ *   w1   bf16 [n_layers][d_g][d_model]            c1  fp32 [n_layers][d_g]
+ *   w2   bf16 [n_layers][n_kv_heads][d_p][d_g]    c2  fp32 [n_layers][n_kv_heads][d_p]
+ *   w_g  fp32 [d_p], b_g                          (n_layers, n_kv_heads: the context's)
+ * All device pointers, caller-owned, w1 and w2 16-byte aligned; d_model a multiple of 256, d_g a
+ * multiple of 64, d_p >= 1. */
+typedef struct {
+    int32_t d_model, d_g, d_p;
+    const void *w1;
+    const float *c1;
+    const void *w2;
+    const float *c2;
+    const float *w_g;
+    float b_g;
+} kvtrim_gate;
+
+/* Bytes of scratch kvtrim_gate_forward needs for n_tok tokens and n_layers layers of a range
+ * (the hidden activations u in fp32); 0 for invalid arguments.  Host-only, no GPU call. */
+size_t kvtrim_gate_scratch_bytes(const kvtrim_gate *g, int32_t n_tok, int32_t n_layers);
+
+/* x: bf16 [layer_end - layer_begin][n_tok][d_model], 16-byte aligned, the representation of each
+ * token at the input of each block of the range.  Writes, for those layers,
+ *   log_beta_out[(tok * n_layers + layer) * n_kv_heads + head] = log sigmoid(z)      (fp32)
+ *   log_tail_out[same index] = log(sum_{k<horizon} beta^k), horizon 0 = the limit -log(1 - beta)
+ *                              (Eq. global_score; NULL to skip; horizon in [0, 4096])
+ * - with one token per sequence this is segment order, the layout kvtrim_append takes.
+ * scratch: device memory, 16-byte aligned, at least kvtrim_gate_scratch_bytes(...) bytes, contents
+ * undefined afterwards.  Enqueues two kernels on the stream; allocates nothing.  Arithmetic: bf16
+ * products accumulated in fp32 on the matrix cores, u kept to 16 mantissa bits for the second
+ * layer; results agree with an fp64 evaluation to about 1e-5 relative in log beta. */
+kvtrim_status kvtrim_gate_forward(kvtrim_ctx *ctx, const kvtrim_gate *g, const void *x, int32_t n_tok,
+                                  int32_t layer_begin, int32_t layer_end, int32_t horizon, void *scratch,
+                                  float *log_beta_out, float *log_tail_out, void *hip_stream);
+
 /* Instrumentation (for the benchmark; not a step of the method).  Between
  * kvtrim_profile_begin and kvtrim_profile_end every launch of a kernel whose bit is
  * set in `kernel_mask` (bit i = kernel id i, names from kvtrim_kernel_name) is
@@ -273,7 +316,7 @@ kvtrim_status kvtrim_paged_attn(kvtrim_ctx *ctx, const kvtrim_paged_cache *c, co
  * end waits for `hip_stream` and writes, per kernel id, the summed duration in
  * milliseconds and the number of bracketed launches into host arrays of
  * KVTRIM_N_KERNELS elements.  Do not capture a HIP graph while profiling is on. */
-#define KVTRIM_N_KERNELS 23
+#define KVTRIM_N_KERNELS 25
 #define KVTRIM_PROFILE_MAX_LAUNCHES 4096
 kvtrim_status kvtrim_profile_begin(kvtrim_ctx *ctx, uint32_t kernel_mask);
 kvtrim_status kvtrim_profile_end(kvtrim_ctx *ctx, void *hip_stream, double *ms_sum_host,

@@ -15,10 +15,11 @@ EXPORTS = ["kvtrim_create", "kvtrim_destroy", "kvtrim_workspace_bytes", "kvtrim_
            "kvtrim_poll_error", "kvtrim_score", "kvtrim_select_global", "kvtrim_compact",
            "kvtrim_decode_attn", "kvtrim_decode_attn_soft", "kvtrim_occupancy", "kvtrim_compact_attn", "kvtrim_append",
            "kvtrim_paged_build", "kvtrim_paged_append", "kvtrim_paged_score", "kvtrim_paged_select",
-           "kvtrim_paged_evict", "kvtrim_paged_attn", "kvtrim_profile_begin", "kvtrim_profile_end",
+           "kvtrim_paged_evict", "kvtrim_paged_attn", "kvtrim_gate_scratch_bytes", "kvtrim_gate_forward",
+           "kvtrim_profile_begin", "kvtrim_profile_end",
            "kvtrim_kernel_name"]
 PAGE_SIZE = 128
-N_KERNELS = 23
+N_KERNELS = 25
 
 
 class KvtrimError(RuntimeError):
@@ -44,6 +45,11 @@ class _PagedCache(C.Structure):
                 ("seg_live", C.c_void_p), ("page_owner", C.c_void_p), ("page_live", C.c_void_p),
                 ("free_list", C.c_void_p), ("n_free", C.c_void_p), ("n_pages", C.c_int32),
                 ("max_pages_per_seg", C.c_int32)]
+
+
+class _Gate(C.Structure):
+    _fields_ = [("d_model", C.c_int32), ("d_g", C.c_int32), ("d_p", C.c_int32), ("w1", C.c_void_p), ("c1", C.c_void_p),
+                ("w2", C.c_void_p), ("c2", C.c_void_p), ("w_g", C.c_void_p), ("b_g", C.c_float)]
 
 
 def library_path():
@@ -89,12 +95,17 @@ def load_library():
         lib.kvtrim_paged_evict.argtypes = [C.c_void_p, P, C.c_void_p, C.c_void_p]
         lib.kvtrim_paged_attn.argtypes = [C.c_void_p, P, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p,
                                           C.c_void_p, C.c_void_p]
+        lib.kvtrim_gate_scratch_bytes.argtypes = [C.POINTER(_Gate), C.c_int32, C.c_int32]
+        lib.kvtrim_gate_scratch_bytes.restype = C.c_size_t
+        lib.kvtrim_gate_forward.argtypes = [C.c_void_p, C.POINTER(_Gate), C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                            C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.kvtrim_profile_begin.argtypes = [C.c_void_p, C.c_uint32]
         lib.kvtrim_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         lib.kvtrim_kernel_name.argtypes = [C.c_int32]
         lib.kvtrim_kernel_name.restype = C.c_char_p
         for name in EXPORTS:
-            if name not in ("kvtrim_workspace_bytes", "kvtrim_last_error", "kvtrim_kernel_name"):
+            if name not in ("kvtrim_workspace_bytes", "kvtrim_last_error", "kvtrim_kernel_name",
+                            "kvtrim_gate_scratch_bytes"):
                 getattr(lib, name).restype = C.c_int
         _lib = lib
     return _lib
@@ -180,6 +191,22 @@ class PagedCache:
                              _ptr(self.block_table).value, _ptr(self.seg_pages).value, _ptr(self.seg_live).value,
                              _ptr(self.page_owner).value, _ptr(self.page_live).value, _ptr(self.free_list).value,
                              _ptr(self.n_free).value, self.n_pages, self.max_pages_per_seg)
+
+
+class Gate:
+    """Retention-gate weights on the device (tensors as made by kvtrim_inputs.gate_weights) plus the C view."""
+
+    def __init__(self, w1, c1, w2, c2, w_g, b_g):
+        self.w1, self.c1, self.w2, self.c2, self.w_g, self.b_g = w1, c1, w2, c2, w_g, float(b_g)
+        self.n_layers, self.d_g, self.d_model = w1.shape
+        self.n_heads, self.d_p = w2.shape[1], w2.shape[2]
+        self.c = _Gate(self.d_model, self.d_g, self.d_p, _ptr(w1, torch.bfloat16).value, _ptr(c1, torch.float32).value,
+                       _ptr(w2, torch.bfloat16).value, _ptr(c2, torch.float32).value, _ptr(w_g, torch.float32).value,
+                       self.b_g)
+
+    @classmethod
+    def from_dict(cls, d, device="cuda"):
+        return cls(*(d[n].to(device).contiguous() for n in ("w1", "c1", "w2", "c2", "w_g")), d["b_g"])
 
 
 class Context:
@@ -314,6 +341,18 @@ def kvtrim_paged_attn(ctx, cache, q, layer_begin, layer_end, softmax_scale, out,
                                                  int(layer_begin), int(layer_end), float(softmax_scale),
                                                  _ptr(out, torch.float32), _ptr(lse, torch.float32),
                                                  _stream(stream)), "kvtrim_paged_attn")
+
+
+def kvtrim_gate_scratch_bytes(gate, n_tok, n_layers):
+    return int(load_library().kvtrim_gate_scratch_bytes(C.byref(gate.c), int(n_tok), int(n_layers)))
+
+
+def kvtrim_gate_forward(ctx, gate, x, n_tok, layer_begin, layer_end, horizon, scratch, log_beta_out, log_tail_out=None,
+                        stream=None):
+    _check(ctx, load_library().kvtrim_gate_forward(
+        ctx.handle, C.byref(gate.c), _ptr(x, torch.bfloat16), int(n_tok), int(layer_begin), int(layer_end), int(horizon),
+        _ptr(scratch), _ptr(log_beta_out, torch.float32), _ptr(log_tail_out, torch.float32), _stream(stream)),
+        "kvtrim_gate_forward")
 
 
 def kvtrim_kernel_name(kernel_id):

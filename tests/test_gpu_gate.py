@@ -1,0 +1,114 @@
+"""GPU parity of the retention-gate forward (Sec. 4.1, weight-tied gates) against the fp64 oracle.
+
+The path is floating point throughout: bf16 weights and inputs, fp32 accumulation on the matrix
+cores, the hidden activations carried to 16 mantissa bits into the second layer.  Tolerance:
+|log beta_gpu - log beta_ref| <= 2e-4 |log beta_ref|: d(log beta)/dz = sigmoid(-z) <= |log beta|, so
+the relative error of log beta is at most the absolute error of the gate logit z, and fp32
+accumulation over <= 4608 products (about sqrt(n) 2^-24 of the summed magnitudes) plus the 2^-17
+split keep that near 1e-5 for the logits of the synthetic gates (|z| < 20); the tests print what
+they measure (1e-6 .. 2e-5).
+"""
+import numpy as np
+import pytest
+import torch
+
+import kvtrim_inputs as ki
+import oracle
+import paper_2605_09649_amd as kv
+from helpers import bf16_bits
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+RTOL = 2e-4
+
+
+def run_both(L, H, d_model, d_g, d_p, n_tok, b_g=3.5, layer_begin=0, layer_end=None, horizon=None, salt=0):
+    layer_end = L if layer_end is None else layer_end
+    w = ki.gate_weights(L, H, d_model, d_g, d_p, b_g=b_g, seed=1234 + salt)
+    x = ki.gate_inputs(L, n_tok, d_model, salt=salt)[layer_begin:layer_end].contiguous()
+    og = oracle.Gate(bf16_bits(w["w1"]), w["c1"].numpy(), bf16_bits(w["w2"]), w["c2"].numpy(), w["w_g"].numpy(), b_g)
+    z_ref, lb_ref, lt_ref = oracle.gate_forward(og, bf16_bits(x), layer_begin, layer_end, horizon)
+    ctx = kv.Context(1, L, H, H, 64, 1024)
+    gate = kv.Gate.from_dict(w, DEV)
+    nl = layer_end - layer_begin
+    scratch = torch.empty(kv.kvtrim_gate_scratch_bytes(gate, n_tok, nl) // 4, dtype=torch.float32, device=DEV)
+    lb = torch.full((n_tok, L, H), float("nan"), dtype=torch.float32, device=DEV)
+    lt = torch.full((n_tok, L, H), float("nan"), dtype=torch.float32, device=DEV) if horizon is not None else None
+    kv.kvtrim_gate_forward(ctx, gate, x.to(DEV), n_tok, layer_begin, layer_end, 0 if horizon is None else horizon,
+                           scratch, lb, lt)
+    assert kv.kvtrim_poll_error(ctx) == 0
+    return z_ref, lb_ref, lt_ref, lb.cpu().numpy(), None if lt is None else lt.cpu().numpy()
+
+
+def rel_err(got, ref):
+    return float(np.max(np.abs(got.astype(np.float64) - ref) / np.abs(ref)))
+
+
+@pytest.mark.parametrize("L,H,d_model,d_g,d_p,n_tok", [
+    (2, 2, 256, 64, 1, 1),            # smallest legal sizes, scalar projection
+    (3, 2, 512, 128, 7, 5),           # d_p not a multiple of the 16-row tile
+    (2, 4, 1024, 512, 128, 16),       # the paper's hidden width, one full token tile
+    (2, 2, 256, 576, 40, 17),         # hidden width beyond one staged chunk, token tail of one
+    (1, 2, 512, 64, 33, 20),          # two token tiles per block
+    (1, 2, 512, 64, 33, 150),         # several blocks of four token tiles and a ragged tail
+])
+def test_gate_forward_matches_the_oracle(L, H, d_model, d_g, d_p, n_tok):
+    z_ref, lb_ref, _, lb, _ = run_both(L, H, d_model, d_g, d_p, n_tok, salt=d_p)
+    assert np.isfinite(lb).all() and (lb <= 0).all()
+    err = rel_err(lb, lb_ref)
+    print(f"max relative error of log beta: {err:.2e} (logits {z_ref.min():.2f} .. {z_ref.max():.2f})")
+    assert err <= RTOL
+
+
+def test_layer_range_leaves_other_layers_alone():
+    _, lb_ref, _, lb, _ = run_both(4, 2, 256, 64, 16, 3, layer_begin=1, layer_end=3)
+    assert np.isnan(lb[:, 0, :]).all() and np.isnan(lb[:, 3, :]).all()
+    assert rel_err(lb[:, 1:3, :], lb_ref[:, 1:3, :]) <= RTOL
+
+
+@pytest.mark.parametrize("horizon", [1, 2, 5, 0])
+def test_horizon_tail_constant(horizon):
+    # Eq. global_score: the factor sum_{k<H} beta^k, cached in log form with log beta
+    _, lb_ref, lt_ref, lb, lt = run_both(2, 2, 256, 128, 32, 9, b_g=1.0, horizon=horizon)
+    assert rel_err(lb, lb_ref) <= RTOL
+    assert np.max(np.abs(lt - lt_ref)) <= 1e-3 * np.max(np.abs(lt_ref)) + 1e-6
+    if horizon == 1:
+        assert np.array_equal(lt, np.zeros_like(lt))
+
+
+def test_initial_bias_of_eighteen_keeps_beta_next_to_one():
+    # Sec. 5.1: b_g starts at 18.0 - log beta is about -1.5e-8 and must not flush to 0 or lose its digits
+    z_ref, lb_ref, _, lb, _ = run_both(2, 2, 256, 64, 16, 4, b_g=18.0)
+    assert (lb < 0).all() and rel_err(lb, lb_ref) <= 2e-3 * np.max(np.abs(z_ref))   # d(log beta)/log beta = -dz here
+
+
+def test_full_size_gate_one_token_and_sixteen():
+    # the benchmark model: 32 layers x 8 KV heads, d_model 4096, hidden width 512 (Sec. 5.1), d_p 128
+    for n_tok in (1, 16):
+        z_ref, lb_ref, _, lb, _ = run_both(32, 8, 4096, 512, 128, n_tok, salt=n_tok)
+        err = rel_err(lb, lb_ref)
+        print(f"n_tok {n_tok}: max relative error of log beta {err:.2e}")
+        assert err <= RTOL
+
+
+def test_host_side_argument_checks_of_the_gate():
+    L, H = 2, 2
+    w = ki.gate_weights(L, H, 256, 64, 8)
+    ctx = kv.Context(1, L, H, H, 64, 1024)
+    gate = kv.Gate.from_dict(w, DEV)
+    x = ki.gate_inputs(L, 2, 256).to(DEV)
+    scratch = torch.empty(2 * L * 64, dtype=torch.float32, device=DEV)
+    lb = torch.zeros(2, L, H, dtype=torch.float32, device=DEV)
+    with pytest.raises(kv.KvtrimError):
+        kv.kvtrim_gate_forward(ctx, gate, x, 0, 0, L, 1, scratch, lb)              # no token
+    with pytest.raises(kv.KvtrimError):
+        kv.kvtrim_gate_forward(ctx, gate, x, 2, 0, L + 1, 1, scratch, lb)          # layer range beyond the model
+    with pytest.raises(kv.KvtrimError):
+        kv.kvtrim_gate_forward(ctx, gate, x, 2, 0, L, 5000, scratch, lb)           # horizon out of range
+    with pytest.raises(kv.KvtrimError):
+        kv.kvtrim_gate_forward(ctx, gate, x, 2, 0, L, 1, None, lb)                 # no scratch
+    w_bad = ki.gate_weights(L, H, 128, 64, 8)
+    with pytest.raises(kv.KvtrimError):                                            # d_model not a multiple of 256
+        kv.kvtrim_gate_forward(ctx, kv.Gate.from_dict(w_bad, DEV), x, 2, 0, L, 1, scratch, lb)
+    assert kv.kvtrim_gate_scratch_bytes(gate, 2, L) == 2 * L * 64 * 4
+    assert kv.kvtrim_gate_scratch_bytes(gate, 0, L) == 0
