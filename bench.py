@@ -45,6 +45,85 @@ def algorithmic_bytes(w, n_cand, n_ret, horizon=1):
     }
 
 
+def bench_gate(args):
+    """Retention-gate forward for tokens entering the cache (not part of the metric's step: there
+    log beta is an input).  One JSON line of its own."""
+    import numpy as np
+    import torch
+    import kvtrim_inputs as ki
+    import paper_2605_09649_amd as kv
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = ki.workload("long")
+    L, H, dm, dg, dp, n_tok = w.n_layers, w.n_kv_heads, w.n_q_heads * w.head_dim, 512, 128, args.gate
+    K, W = args.steps, max(args.warmup, 1)
+    wts = ki.gate_weights(L, H, dm, dg, dp, device=dev)
+    gate = kv.Gate.from_dict(wts, dev)
+    ctx = kv.Context(1, L, H, w.n_q_heads, w.head_dim, 1024)
+    horizon = args.horizon
+    xs = [ki.gate_inputs(L, n_tok, dm, device=dev, salt=i) for i in range(4)]
+    scratch = torch.empty(kv.kvtrim_gate_scratch_bytes(gate, n_tok, L) // 4, dtype=torch.float32, device=dev)
+    lb = torch.zeros(n_tok, L, H, dtype=torch.float32, device=dev)
+    lt = torch.zeros(n_tok, L, H, dtype=torch.float32, device=dev) if horizon != 1 else None
+    for i in range(W):
+        kv.kvtrim_gate_forward(ctx, gate, xs[i % 4], n_tok, 0, L, horizon, scratch, lb, lt)
+    torch.cuda.synchronize()
+    kv.kvtrim_profile_begin(ctx, (1 << 23) | (1 << 24))          # k_gate_hidden, k_gate_readout
+    t0 = time.perf_counter()
+    for i in range(K):
+        kv.kvtrim_gate_forward(ctx, gate, xs[i % 4], n_tok, 0, L, horizon, scratch, lb, lt)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = kv.kvtrim_profile_end(ctx)
+    assert kv.kvtrim_poll_error(ctx) == 0
+    ms = (t1 - t0) * 1e3 / K
+    h_ms = prof["k_gate_hidden"][0] / prof["k_gate_hidden"][1]
+    r_ms = prof["k_gate_readout"][0] / prof["k_gate_readout"][1]
+    # first layer: W1 once per 64 tokens of a call, x once per 16-row tile group (cached), u written once
+    w1_bytes = L * dg * dm * 2
+    w2_bytes = L * H * dp * dg * 2
+    alg_hidden = w1_bytes + L * n_tok * dm * 2 + L * n_tok * dg * 4
+    flops_hidden = 2.0 * n_tok * L * dg * dm
+    if n_tok <= 64:
+        roof = {"bound": "hbm", "kernel": "k_gate_hidden", "achieved": alg_hidden / (h_ms * 1e-3) / 1e9,
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": None, "algorithmic_bytes_per_launch": alg_hidden}
+    else:
+        roof = {"bound": "mfma", "kernel": "k_gate_hidden", "achieved": flops_hidden / (h_ms * 1e-3) / 1e12,
+                "peak": 2500.0, "unit": "TFLOP/s", "traffic": None, "flops_per_launch": flops_hidden}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["avg_launch_ms"] = h_ms
+    roof["second_kernel"] = {"kernel": "k_gate_readout", "avg_launch_ms": r_ms,
+                             "achieved": (w2_bytes + L * n_tok * dg * 4) / (r_ms * 1e-3) / 1e9, "unit": "GB/s"}
+    log(f"[bench] gate forward, {n_tok} token(s): {ms:.4f} ms/call; k_gate_hidden {h_ms * 1e3:.1f} us, "
+        f"k_gate_readout {r_ms * 1e3:.1f} us; {roof['achieved']:.0f} {roof['unit']}")
+    result = {
+        "metric": "retention-gate forward (32Lx8H, d_model 4096, d_g 512, d_p 128), tokens/s", "value": n_tok * 1e3 / ms,
+        "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"gate forward for {n_tok} token(s) per call into all {L * H} (layer, KV head) lists; "
+                               f"random weights, lookahead horizon {horizon if horizon > 0 else 'infinite'}"},
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        from helpers import bf16_bits
+        og = oracle.Gate(bf16_bits(wts["w1"]), wts["c1"].cpu().numpy(), bf16_bits(wts["w2"]), wts["c2"].cpu().numpy(),
+                         wts["w_g"].cpu().numpy(), wts["b_g"])
+        ns = min(n_tok, 4)                       # bounded sample: the first tokens of the last call's input
+        x_last = xs[(K - 1) % 4][:, :ns].contiguous()
+        t_cpu = time.perf_counter()
+        _, lb_ref, _ = oracle.gate_forward(og, bf16_bits(x_last))
+        cpu_s = time.perf_counter() - t_cpu
+        err = float(np.max(np.abs(lb[:ns].cpu().numpy() - lb_ref) / np.abs(lb_ref)))
+        log(f"[bench] oracle gate forward for {ns} token(s): {cpu_s:.2f} s; GPU vs oracle: max rel err of log beta {err:.2e}")
+        assert err <= 2e-4, "GPU gate disagrees with the oracle"
+        result["cpu_baseline"] = {"value": ns / cpu_s, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"the first {ns} token(s) of one call, all layers and heads, one thread"}
+        result["parity_on_sampled_step"] = {"log_beta_max_rel_err": err}
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -65,7 +144,15 @@ def main():
     ap.add_argument("--kernel-times", action="store_true",
                     help="bracket every kernel with HIP events and print the per-kernel averages to stderr "
                          "(the events add a little to ms_per_step)")
+    ap.add_argument("--gate", type=int, default=0, metavar="N_TOK",
+                    help="time the retention-gate forward alone (the metric model's shape: 32 layers x 8 KV heads, "
+                         "d_model 4096, hidden width 512, projection width 128) for N_TOK tokens per call")
     args = ap.parse_args()
+    if args.gate:
+        if args.gpus != 1:
+            print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+            sys.exit(2)
+        return bench_gate(args)
     if args.paged and args.unfused:
         ap.error("--paged and --unfused exclude each other")
     if args.gpus != 1:
