@@ -50,7 +50,10 @@ def rel_err(got, ref):
     (2, 4, 1024, 512, 128, 16),       # the paper's hidden width, one full token tile
     (2, 2, 256, 576, 40, 17),         # hidden width beyond one staged chunk, token tail of one
     (1, 2, 512, 64, 33, 20),          # two token tiles per block
-    (1, 2, 512, 64, 33, 150),         # several blocks of four token tiles and a ragged tail
+    (1, 2, 512, 64, 33, 64),          # four token tiles in one block
+    (1, 2, 512, 64, 33, 150),         # LDS-tiled first layer: hidden width below the 128-row tile, ragged token tail
+    (2, 2, 256, 192, 16, 300),        # ... 1.5 row tiles, 2.3 token tiles
+    (1, 1, 1024, 512, 128, 257),      # ... the paper's hidden width, one token beyond two tiles
 ])
 def test_gate_forward_matches_the_oracle(L, H, d_model, d_g, d_p, n_tok):
     z_ref, lb_ref, _, lb, _ = run_both(L, H, d_model, d_g, d_p, n_tok, salt=d_p)
