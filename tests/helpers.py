@@ -32,3 +32,16 @@ def live_mask(hc):
     for s, n in zip(hc.seg_start, hc.seg_len):
         m[s:s + n] = True
     return m
+
+
+def paper_constants():
+    """The values the paper prints that tests refer to (tests/golden/paper_constants.txt)."""
+    import os
+    out = {}
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_constants.txt")) as f:
+        for line in f:
+            line = line.split("#")[0].split()
+            if line:
+                vals = [float(v) if "." in v else int(v) for v in line[1:]]
+                out[line[0]] = vals[0] if len(vals) == 1 else vals
+    return out

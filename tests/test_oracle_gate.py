@@ -7,7 +7,9 @@ import torch.nn.functional as F
 
 import kvtrim_inputs as ki
 import oracle
-from helpers import bf16_bits, bits_to_f64
+from helpers import bf16_bits, paper_constants
+
+PAPER = paper_constants()
 
 
 def make_gate(L=3, H=2, d_model=48, d_g=20, d_p=7, b_g=0.75, seed=1):
@@ -41,10 +43,12 @@ def test_matches_torch_fp64_on_non_square_shapes_and_layer_ranges():
 
 def test_zero_projection_gives_the_tied_bias_alone():
     # Sec. 5.1: b_g starts at 18.0; with Proj = 0 every gate is sigmoid(18)
-    w, _ = make_gate(b_g=18.0)
+    assert PAPER["gate_bias_init"] == 18.0
+    w, _ = make_gate(b_g=PAPER["gate_bias_init"])
     for name in ("w1", "c1", "c2"):
         w[name] = torch.zeros_like(w[name])
-    g = oracle.Gate(bf16_bits(w["w1"]), w["c1"].numpy(), bf16_bits(w["w2"]), w["c2"].numpy(), w["w_g"].numpy(), 18.0)
+    g = oracle.Gate(bf16_bits(w["w1"]), w["c1"].numpy(), bf16_bits(w["w2"]), w["c2"].numpy(), w["w_g"].numpy(),
+                    PAPER["gate_bias_init"])
     z, lb, _ = oracle.gate_forward(g, bf16_bits(ki.gate_inputs(3, 4, 48)))
     assert np.array_equal(z, np.full_like(z, 18.0))
     e = 1.0
@@ -127,7 +131,8 @@ def test_horizon_tail_matches_the_series_and_the_cached_constant_of_the_score():
     _, lb, lt1 = oracle.gate_forward(g, x, horizon=1)
     assert np.array_equal(lt1, np.zeros_like(lt1))
     beta = np.exp(lb)
-    for H in (2, 5):
+    assert PAPER["inference_horizon"] in PAPER["ablation_horizons"]
+    for H in PAPER["ablation_horizons"][1:]:
         _, _, lt = oracle.gate_forward(g, x, horizon=H)
         direct = np.log(sum(beta ** k for k in range(H)))
         assert np.allclose(lt, direct, rtol=1e-13, atol=1e-15)
@@ -140,7 +145,7 @@ def test_horizon_tail_matches_the_series_and_the_cached_constant_of_the_score():
 
 
 def test_synthetic_gate_has_the_spread_of_the_workload_logits():
-    w = ki.gate_weights(4, 2, 256, 512, 128, b_g=3.5)
+    w = ki.gate_weights(4, 2, 256, PAPER["gate_hidden_width"], 128, b_g=3.5)
     g = oracle.Gate(bf16_bits(w["w1"]), w["c1"].numpy(), bf16_bits(w["w2"]), w["c2"].numpy(), w["w_g"].numpy(), 3.5)
     z, lb, _ = oracle.gate_forward(g, bf16_bits(ki.gate_inputs(4, 64, 256)))
     assert abs(z.mean() - 3.5) < 1.0 and 0.8 < z.std() < 2.5
