@@ -69,7 +69,8 @@ typedef struct {
     int32_t n_kv_heads; /* Hkv >= 1 */
     int32_t n_q_heads;  /* Hq, a multiple of Hkv, Hq/Hkv <= 8 */
     int32_t head_dim;   /* D: 64 or 128 */
-    int64_t max_entries; /* largest cap_entries of any cache passed to this context */
+    int64_t max_entries; /* largest cap_entries of any cache passed to this context; 1 .. 2^31 - 4096
+                          * (entries of a segment are indexed with 32-bit integers plus a chunk of slack) */
 } kvtrim_config;
 
 typedef struct {

@@ -51,7 +51,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const 
         const int kp = kept[i];
         acc[4] |= (len < 0 || st < 0 || st + len > src.cap);
         acc[5] |= (kp < 0 || kp > len);
-        const int64_t nch = len > 0 ? (len + CMP_CHUNK - 1) / CMP_CHUNK : 0;
+        const int64_t nch = len > 0 ? ((int64_t)len + CMP_CHUNK - 1) / CMP_CHUNK : 0;
         const int64_t need = ((int64_t)kp + reserve + align - 1) / align * align;   // align = 1 unless pages are built
         acc[3] += nch;
         acc[2] += need;

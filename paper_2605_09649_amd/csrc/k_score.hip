@@ -19,10 +19,10 @@ __global__ __launch_bounds__(256) void k_score(CacheView c, const int32_t* __res
     float* out = score + start;
     if (c.log_tail) {
         const float* lt = c.log_tail + start;
-        for (int j = part * 256 + threadIdx.x; j < len; j += bps * 256)
+        for (int64_t j = part * 256 + threadIdx.x; j < len; j += bps * 256)
             out[j] = __fmaf_rn((float)(t1 - pos[j]), lb[j], lt[j]);
     } else {
-        for (int j = part * 256 + threadIdx.x; j < len; j += bps * 256)
+        for (int64_t j = part * 256 + threadIdx.x; j < len; j += bps * 256)
             out[j] = __fmul_rn((float)(t1 - pos[j]), lb[j]);
     }
 }
@@ -58,7 +58,7 @@ __global__ __launch_bounds__(256) void k_occupancy(CacheView c, const int32_t* _
     const float* lb = c.log_beta + start;
     const int32_t* pos = c.pos + start;
     double sum = 0.0;
-    for (int j = part * 256 + threadIdx.x; j < len; j += bps * 256)
+    for (int64_t j = part * 256 + threadIdx.x; j < len; j += bps * 256)
         sum += (double)__builtin_amdgcn_exp2f((float)(t - pos[j]) * lb[j] * 1.4426950408889634f);
     sum = block_sum<double>(sum, lds);
     if (threadIdx.x == 0 && sum != 0.0) atomicAdd(&occ[seq], sum);

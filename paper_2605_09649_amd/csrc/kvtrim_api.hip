@@ -26,7 +26,7 @@ static bool config_ok(const kvtrim_config* c) {
     const int g = c->n_q_heads / c->n_kv_heads;
     if (g < 1 || g > 8) return false;
     if (c->head_dim != 64 && c->head_dim != 128) return false;
-    if (c->max_entries < 1 || c->max_entries > ((int64_t)1 << 31) - 1) return false;
+    if (c->max_entries < 1 || c->max_entries > ((int64_t)1 << 31) - 4096) return false;
     const int64_t nseg = (int64_t)c->n_seq * c->n_layers * c->n_kv_heads;
     if (nseg > (1 << 24) || c->n_seq > 65536) return false;
     return true;

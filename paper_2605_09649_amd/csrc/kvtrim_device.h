@@ -100,7 +100,7 @@ __device__ __forceinline__ int build_chunk_table(const int32_t* __restrict__ seg
             const int64_t st = seg_start[g];
             const int64_t nxt = (g + 1 < nseg) ? seg_start[g + 1] : cap;
             if (len < 0 || st < 0 || st + len > cap || st + len > nxt) s_bad = 1;
-            else if (in_range(g) && len > 0) v = ((uint64_t)len << 32) | (uint64_t)((len + chunk - 1) / chunk);
+            else if (in_range(g) && len > 0) v = ((uint64_t)len << 32) | (uint64_t)(((int64_t)len + chunk - 1) / chunk);
         }
         uint64_t tot;
         block_excl_scan<uint64_t>(v, s_scan, &tot);
@@ -127,7 +127,7 @@ __device__ __forceinline__ int build_chunk_table(const int32_t* __restrict__ seg
         if (g < nseg) {
             len = seg_len[g];
             st = seg_start[g];
-            if (in_range(g) && len > 0) v = ((uint64_t)len << 32) | (uint64_t)((len + chunk - 1) / chunk);
+            if (in_range(g) && len > 0) v = ((uint64_t)len << 32) | (uint64_t)(((int64_t)len + chunk - 1) / chunk);
         }
         if (threadIdx.x == 0) s_nbig = 0;
         uint64_t tot;
@@ -158,7 +158,7 @@ __device__ __forceinline__ int build_chunk_table(const int32_t* __restrict__ seg
             const int gg = s_big_g[b], cc = s_big_c0[b];
             const int ll = seg_len[gg];
             const int64_t ss = seg_start[gg];
-            const int nn = (ll + chunk - 1) / chunk;
+            const int nn = (int)(((int64_t)ll + chunk - 1) / chunk);
             for (int i = lane; i < nn; i += 64) {
                 ChunkDesc d;
                 d.first = ss + (int64_t)i * chunk;

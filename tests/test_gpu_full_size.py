@@ -223,3 +223,77 @@ def test_long_128k_paged_steady_state():
         assert ph.structure_problems() == [] and ph.equals(hc), step
         assert attn_error(out.cpu().numpy(), out_ref) <= ATTN_TOL
         assert np.abs(lse.cpu().numpy() - lse_ref).max() <= 2e-3
+
+
+def test_a_billion_candidates_score_and_select_properties():
+    # Stages 1-2 at 2^30 candidates (half of the library's limit; 32x the benchmark's first eviction): one giant
+    # segment, ragged and empty ones, two sequences with very different budgets, and quantised log beta so that
+    # exact score ties are everywhere.  The oracle's full sort is out of reach at this size, so the score is
+    # checked against it on a sample and the selection through the properties that define it:
+    #   count(key > thr) < B <= count(key >= thr);  every key > thr kept, every key < thr evicted;
+    #   the kept ties are the first B - count(key > thr) ties in (layer, head, position) = storage order;
+    #   kept[g] = survivors of segment g;  sum(kept) = B.
+    w = ki.Workload("huge", 0, 2, 4, 2, 4, 64, (0, 0), (0, 0), 1, 3.0, 1.5)
+    total = 1 << 30
+    seg_len = np.array([600_000_000, 0, 1, 2049, 150_000_000, 0, 30_000_000, 0,
+                        100_000_000, 90_000_000, 0, 0, 50_000_000, 40_000_000, 0, 0], np.int64)
+    seg_len[15] = total - seg_len.sum()
+    assert seg_len.min() >= 0 and seg_len.sum() == total and len(seg_len) == w.nseg
+    starts = np.concatenate([[0], np.cumsum(seg_len)[:-1]])
+    g = torch.Generator(device=DEV).manual_seed(2030)
+    lb = torch.empty(total, dtype=torch.float32, device=DEV)
+    pos = torch.empty(total, dtype=torch.int32, device=DEV)
+    for s, n in zip(starts, seg_len):
+        if n:
+            q = torch.randint(1, 4097, (int(n),), generator=g, device=DEV, dtype=torch.int32)
+            lb[s:s + n] = q.to(torch.float32) * (-1.0 / 4096.0)                  # beta in [e^-1, 1): exact multiples of 2^-12
+            pos[s:s + n] = torch.arange(int(n), dtype=torch.int32, device=DEV)
+            del q
+    now = np.array([int(seg_len[:8].max()), int(seg_len[8:].max())], np.int32)
+    dummy = torch.zeros(1, w.head_dim, dtype=torch.bfloat16, device=DEV)      # stages 1-2 never touch K / V
+    cache = kv.Cache(dummy, dummy, lb, pos, torch.from_numpy(starts).to(DEV), torch.from_numpy(seg_len.astype(np.int32)).to(DEV))
+    ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, total)
+    score = torch.empty(total, dtype=torch.float32, device=DEV)
+    keep = torch.empty(total, dtype=torch.uint8, device=DEV)
+    kept = torch.zeros(w.nseg, dtype=torch.int32, device=DEV)
+    thr = torch.zeros(w.n_seq, dtype=torch.int32, device=DEV)
+    n_seq0 = int(seg_len[:8].sum())
+    budgets = [int(0.37 * n_seq0), 12345]
+    kv.kvtrim_score(ctx, cache, torch.from_numpy(now).to(DEV), score)
+    kv.kvtrim_select_global(ctx, cache, score, torch.tensor(budgets, dtype=torch.int64, device=DEV), keep, kept, thr)
+    assert kv.kvtrim_poll_error(ctx) == 0
+
+    # score: a sample against the oracle, bit for bit
+    rng = np.random.default_rng(5)
+    idx = np.unique(np.concatenate([rng.integers(0, total, 200_000), starts[seg_len > 0], (starts + seg_len - 1)[seg_len > 0]]))
+    seg_of = np.searchsorted(starts + seg_len, idx, side="right")
+    cnt = np.bincount(seg_of, minlength=w.nseg).astype(np.int32)
+    idx_dev = torch.from_numpy(idx).to(DEV)
+    empty = np.zeros((0, w.head_dim), np.uint16)
+    sample = oracle.HostCache.from_arrays(shape_of(w), empty, empty, lb[idx_dev].cpu().numpy(), pos[idx_dev].cpu().numpy(),
+                                          np.concatenate([[0], np.cumsum(cnt)[:-1]]).astype(np.int64), cnt)
+    assert np.array_equal(oracle.score(sample, now).view(np.uint32), score[idx_dev].cpu().numpy().view(np.uint32))
+
+    # selection: the defining properties, per sequence
+    thr_u = thr.cpu().numpy().view(np.uint32)
+    kept_h = kept.cpu().numpy()
+    for seq, (a, b) in enumerate([(0, n_seq0), (n_seq0, total)]):
+        B = budgets[seq]
+        u = score[a:b].view(torch.int32).to(torch.int64) & 0xFFFFFFFF
+        key = torch.where(u >= 0x80000000, 0xFFFFFFFF - u, u | 0x80000000)
+        del u
+        t = int(thr_u[seq])
+        k = keep[a:b]
+        gt = key > t
+        n_gt, n_ge = int(gt.sum()), int((key >= t).sum())
+        assert n_gt < B <= n_ge, (seq, n_gt, B, n_ge)
+        assert bool(k[gt].all()) and not bool(k[key < t].any())
+        ties = torch.nonzero(key == t).flatten()
+        kt = k[ties]
+        q = B - n_gt
+        assert int(kt.sum()) == q and bool(kt[:q].all())                  # the first q ties in storage order, no others
+        assert int(k.sum()) == B
+        print(f"sequence {seq}: {b - a} candidates, budget {B}, {n_ge - n_gt} ties at the threshold, {q} of them kept")
+        del key, gt, ties, kt
+    for gidx, (s, n) in enumerate(zip(starts, seg_len)):
+        assert int(keep[s:s + n].sum()) == int(kept_h[gidx]), gidx
