@@ -177,13 +177,16 @@ kvtrim_status kvtrim_compact_attn(kvtrim_ctx *ctx, const kvtrim_cache *src, cons
                                   float *lse, void *hip_stream);
 
 /* Support - new tokens enter the cache (Sec. 3.2: beta is fixed when the token is
- * first cached).  Appends n_new entries to every segment, in order, behind its
- * current end and adds n_new to seg_len.  k_new, v_new: device bf16
+ * first cached).  Appends up to n_new entries to every segment, in order, behind its
+ * current end and adds their number to seg_len.  k_new, v_new: device bf16
  * [nseg][n_new][head_dim]; log_beta_new: device fp32 [nseg][n_new]; log_tail_new:
  * device fp32 [nseg][n_new], required iff c->log_tail != NULL (NULL otherwise); pos_new:
- * device int32 [nseg][n_new] (ascending, above the segment's last position).
- * Device-side error KVTRIM_ECAP if some segment lacks n_new free slots before the
- * next segment (or the end of the buffer); that segment is then left unchanged. */
+ * device int32 [nseg][n_new] (ascending, above the segment's last position).  A
+ * segment takes its rows up to the first one with a NEGATIVE position: the sequences
+ * of a batch may bring different numbers of tokens (a ragged last chunk of a prefill),
+ * the rest of their rows is padding.
+ * Device-side error KVTRIM_ECAP if some segment lacks free slots for its rows before
+ * the next segment (or the end of the buffer); that segment is then left unchanged. */
 kvtrim_status kvtrim_append(kvtrim_ctx *ctx, kvtrim_cache *c, const void *k_new, const void *v_new,
                             const float *log_beta_new, const float *log_tail_new, const int32_t *pos_new,
                             int32_t n_new, void *hip_stream);
@@ -239,8 +242,9 @@ kvtrim_status kvtrim_paged_build(kvtrim_ctx *ctx, const kvtrim_cache *src, const
                                  const int32_t *kept, kvtrim_paged_cache *dst, void *hip_stream);
 
 /* One new token per segment (k_new, v_new: bf16 [nseg][head_dim]; log_beta_new, pos_new:
- * [nseg]; log_tail_new iff the cache carries log_tail): it takes an empty slot of the
- * segment's pages, or the first slot of a page from the free list.  KVTRIM_ECAP when no page is
+ * [nseg]; log_tail_new iff the cache carries log_tail; a negative position = no token for
+ * that segment): it takes an empty slot of the segment's pages, or the first slot of a page
+ * from the free list.  KVTRIM_ECAP when no page is
  * free or the block table is full (that segment is then left unchanged). */
 kvtrim_status kvtrim_paged_append(kvtrim_ctx *ctx, kvtrim_paged_cache *c, const void *k_new, const void *v_new,
                                   const float *log_beta_new, const float *log_tail_new, const int32_t *pos_new,

@@ -265,3 +265,14 @@ def gate_inputs(n_layers: int, n_tok: int, d_model: int, device="cpu", salt: int
     """Token representations entering each transformer block, bf16 [n_layers][n_tok][d_model], N(0,1)."""
     g = torch.Generator(device=device).manual_seed(BASE_SEED + 78 + 1000003 * int(salt))
     return torch.randn(n_layers, n_tok, d_model, generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
+
+
+def chunk_inputs(w: Workload, n_tok: int, device="cpu", *salt):
+    """n_tok new tokens for every segment (a prefill chunk): K, V bf16 [nseg][n_tok][D] ~ N(0,1) and
+    log(beta) fp32 [nseg][n_tok] from the workload's base z distribution."""
+    g = _gen(w, device, 8, *salt)
+    nseg, D = w.nseg, w.head_dim
+    k = torch.randn(nseg, n_tok, D, generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
+    v = torch.randn(nseg, n_tok, D, generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
+    z = torch.randn(nseg, n_tok, generator=g, device=device, dtype=torch.float64) * w.z_std + w.z_mean
+    return {"k_new": k, "v_new": v, "log_beta_new": _log_beta_of_z(z)}

@@ -334,13 +334,18 @@ int kvo_append(const kvo_shape *sh, kvo_cache *c, const uint16_t *k_new, const u
                const float *log_beta_new, const float *log_tail_new, const int32_t *pos_new, int32_t n_new) {
     int64_t nseg = kvo_nseg(sh);
     int D = sh->head_dim;
+    /* a segment takes its new rows up to the first one with a negative position (padding) */
     for (int64_t g = 0; g < nseg; ++g) {
+        int32_t cnt = 0;
+        while (cnt < n_new && pos_new[g * n_new + cnt] >= 0) ++cnt;
         int64_t end = c->seg_start[g] + c->seg_len[g];
         int64_t limit = (g + 1 < nseg) ? c->seg_start[g + 1] : c->cap;
-        if (end + n_new > limit) return -4;
+        if (end + cnt > limit) return -4;
     }
     for (int64_t g = 0; g < nseg; ++g) {
-        for (int32_t r = 0; r < n_new; ++r) {
+        int32_t cnt = 0;
+        while (cnt < n_new && pos_new[g * n_new + cnt] >= 0) ++cnt;
+        for (int32_t r = 0; r < cnt; ++r) {
             int64_t e = c->seg_start[g] + c->seg_len[g] + r;
             memcpy(c->k + e * D, k_new + (g * n_new + r) * D, (size_t)D * 2);
             memcpy(c->v + e * D, v_new + (g * n_new + r) * D, (size_t)D * 2);
@@ -348,7 +353,7 @@ int kvo_append(const kvo_shape *sh, kvo_cache *c, const uint16_t *k_new, const u
             if (c->log_tail && log_tail_new) c->log_tail[e] = log_tail_new[g * n_new + r];
             c->pos[e] = pos_new[g * n_new + r];
         }
-        c->seg_len[g] += n_new;
+        c->seg_len[g] += cnt;
     }
     return 0;
 }

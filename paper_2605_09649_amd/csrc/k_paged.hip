@@ -89,6 +89,7 @@ __global__ __launch_bounds__(256) void k_pg_append(PagedView pc, const uint16_t*
     const int lane = lane_id();
     const int g = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (g >= nseg) return;                                           // uniform over the wavefront
+    if (pos_new[g] < 0) return;                                      // padding: this segment brings no token
     const int npg = pc.seg_pages[g];
     if (npg < 0 || npg > pc.max_pps) {
         if (lane == 0) atomicOr(err, ERR_LAYOUT);

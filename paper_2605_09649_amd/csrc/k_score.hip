@@ -77,19 +77,29 @@ kvtrim_status launch_occupancy(kvtrim_ctx* ctx, const CacheView& c, const int32_
     return KVTRIM_OK;
 }
 
-// One block per segment: copies the n_new rows behind the segment's end (16 bytes per lane)
-// and the per-entry metadata, then bumps seg_len.  A segment without room is left alone.
+// One block per segment: copies the segment's new rows behind its end (16 bytes per lane) and the
+// per-entry metadata, then bumps seg_len.  A segment takes its rows up to the first one with a
+// negative position (sequences of a batch may bring different numbers of tokens: the others are
+// padding).  A segment without room is left alone.
 __global__ __launch_bounds__(256) void k_append(CacheViewMut c, const uint16_t* __restrict__ k_new,
                                                 const uint16_t* __restrict__ v_new,
                                                 const float* __restrict__ lb_new,
                                                 const float* __restrict__ lt_new,
                                                 const int32_t* __restrict__ pos_new, int n_new, int nseg,
                                                 int head_dim, int32_t* err) {
+    __shared__ int s_cnt;
     const int seg = blockIdx.x;
+    if (threadIdx.x == 0) s_cnt = n_new;
+    __syncthreads();
+    for (int i = threadIdx.x; i < n_new; i += blockDim.x)
+        if (pos_new[(int64_t)seg * n_new + i] < 0) atomicMin(&s_cnt, i);
+    __syncthreads();
+    const int cnt = s_cnt;                                        // rows before the first padding row
+    if (cnt == 0) return;
     const int len = c.seg_len[seg];
     const int64_t start = c.seg_start[seg];
     const int64_t limit = (seg + 1 < nseg) ? c.seg_start[seg + 1] : c.cap;
-    if (len < 0 || start < 0 || limit > c.cap || start + len + n_new > limit) {
+    if (len < 0 || start < 0 || limit > c.cap || start + len + cnt > limit) {
         if (threadIdx.x == 0) atomicOr(err, ERR_CAP);
         return;
     }
@@ -98,17 +108,17 @@ __global__ __launch_bounds__(256) void k_append(CacheViewMut c, const uint16_t* 
     const uint4* vs = reinterpret_cast<const uint4*>(v_new) + (int64_t)seg * n_new * vec_per_row;
     uint4* kd = reinterpret_cast<uint4*>(c.k) + (start + len) * vec_per_row;
     uint4* vd = reinterpret_cast<uint4*>(c.v) + (start + len) * vec_per_row;
-    for (int i = threadIdx.x; i < n_new * vec_per_row; i += blockDim.x) {
+    for (int i = threadIdx.x; i < cnt * vec_per_row; i += blockDim.x) {
         kd[i] = ks[i];
         vd[i] = vs[i];
     }
-    for (int i = threadIdx.x; i < n_new; i += blockDim.x) {
+    for (int i = threadIdx.x; i < cnt; i += blockDim.x) {
         c.log_beta[start + len + i] = lb_new[(int64_t)seg * n_new + i];
         if (c.log_tail) c.log_tail[start + len + i] = lt_new[(int64_t)seg * n_new + i];
         c.pos[start + len + i] = pos_new[(int64_t)seg * n_new + i];
     }
     __syncthreads();
-    if (threadIdx.x == 0) c.seg_len[seg] = len + n_new;
+    if (threadIdx.x == 0) c.seg_len[seg] = len + cnt;
 }
 
 kvtrim_status launch_append(kvtrim_ctx* ctx, const CacheViewMut& c, const uint16_t* k_new, const uint16_t* v_new,

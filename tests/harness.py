@@ -136,3 +136,94 @@ def run_steps_both(w, steps, budget, device="cuda:0", reserve=1, cache_dict=None
         gpu.advance(dst)
         hc = hc_next
     return results
+
+
+def run_multiturn_both(w, lengths, chunk, decode_per_turn, budget, device="cuda:0", turns=4, fused=True):
+    """The chunked multi-turn flow: every sequence's tokens are split into `turns` turns; a turn appends its tokens
+    in chunks of `chunk` (sequences run out at different times: their rows are padded with negative positions) and
+    after every chunk the cache is rescored, selected and compacted (no attention); then `decode_per_turn` tokens
+    are decoded with full steps.  Both sides start from empty caches.  Returns one dict of findings per call group."""
+    per_seq = w.n_layers * w.n_kv_heads
+    S, nseg, D = w.n_seq, w.nseg, w.head_dim
+    reserve = chunk                                                # room behind every segment for the next chunk
+    cap = sum(min(int(budget[s]), (lengths[s] + turns * decode_per_turn) * per_seq) for s in range(S)) + nseg * reserve + chunk * nseg + 8
+    shape = oracle.Shape(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim)
+    starts = np.arange(nseg, dtype=np.int64) * reserve
+    hc = oracle.HostCache(shape, cap)
+    hc.seg_start[:] = starts
+    caches = [kv.Cache.empty(nseg, D, cap, device) for _ in range(2)]
+    caches[0].seg_start.copy_(torch.from_numpy(starts))
+    cur, flip = caches[0], 1
+    ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, D, cap)
+    score = torch.zeros(cap, dtype=torch.float32, device=device)
+    keep = torch.zeros(cap, dtype=torch.uint8, device=device)
+    kept = torch.zeros(nseg, dtype=torch.int32, device=device)
+    thr = torch.zeros(S, dtype=torch.int32, device=device)
+    budget_np = np.array(list(budget), np.int64)
+    budget_dev = torch.from_numpy(budget_np).to(device)
+    out = torch.zeros(S, w.n_layers, w.n_q_heads, D, dtype=torch.float32, device=device)
+    lse = torch.zeros(S, w.n_layers, w.n_q_heads, dtype=torch.float32, device=device)
+    scale = 1.0 / math.sqrt(D)
+    next_pos = np.zeros(S, np.int64)                               # position of the next token of each sequence
+    results = []
+
+    def select_compact(pos_new, n_new, inp, attend_q, label):
+        nonlocal hc, cur, flip
+        now = (next_pos - 1).astype(np.int32)
+        # ---- oracle
+        oracle.append(hc, bf16_bits(inp["k_new"]), bf16_bits(inp["v_new"]), inp["log_beta_new"].numpy(), pos_new)
+        s_ref = oracle.score(hc, now)
+        k_ref, kept_ref, thr_ref = oracle.select(hc, s_ref, budget_np)
+        hc_next = oracle.compact(hc, k_ref, cap, reserve)
+        # ---- GPU
+        d = {k: v.to(device) for k, v in inp.items()}
+        kv.kvtrim_append(ctx, cur, d["k_new"], d["v_new"], d["log_beta_new"], torch.from_numpy(pos_new).to(device), n_new)
+        kv.kvtrim_score(ctx, cur, torch.from_numpy(now).to(device), score)
+        kv.kvtrim_select_global(ctx, cur, score, budget_dev, keep, kept, thr)
+        dst = caches[flip]
+        res = {"what": label}
+        if attend_q is None:
+            kv.kvtrim_compact(ctx, cur, keep, kept, dst, reserve)
+        elif fused:
+            kv.kvtrim_compact_attn(ctx, cur, keep, kept, dst, reserve, attend_q.to(device), 0, w.n_layers, scale, out, lse)
+        else:
+            kv.kvtrim_compact(ctx, cur, keep, kept, dst, reserve)
+            kv.kvtrim_decode_attn(ctx, dst, attend_q.to(device), 0, w.n_layers, scale, out, lse)
+        res["status"] = kv.kvtrim_poll_error(ctx)
+        live = live_mask(hc)
+        res["score_equal"] = bool(np.array_equal(score[:cap].cpu().numpy()[live].view(np.uint32), s_ref[live].view(np.uint32)))
+        res["keep_equal"] = bool(np.array_equal(keep[:cap].cpu().numpy()[live], k_ref[live])
+                                 and np.array_equal(kept.cpu().numpy(), kept_ref)
+                                 and np.array_equal(thr.cpu().numpy().view(np.uint32), thr_ref))
+        res["cache_equal"] = compare_caches(device_cache_to_host(w, dst), hc_next)
+        res["entries"] = int(kept_ref.sum())
+        if attend_q is not None:
+            out_ref, lse_ref = oracle.attend(hc_next, bf16_bits(attend_q), scale)
+            res["attn_err"] = attn_error(out.cpu().numpy(), out_ref)
+            fin = np.isfinite(lse_ref)
+            res["lse_err"] = float(np.abs(lse.cpu().numpy()[fin] - lse_ref[fin]).max()) if fin.any() else 0.0
+        results.append(res)
+        hc, cur, flip = hc_next, dst, flip ^ 1
+
+    turn_len = [[(lengths[s] // turns) + (lengths[s] % turns if t == turns - 1 else 0) for t in range(turns)] for s in range(S)]
+    for t in range(turns):
+        left = np.array([turn_len[s][t] for s in range(S)], np.int64)
+        c = 0
+        while left.max() > 0:
+            take = np.minimum(left, chunk)
+            pos_new = np.full((nseg, chunk), -1, np.int32)
+            for s in range(S):
+                row = np.full(chunk, -1, np.int32)
+                row[:take[s]] = next_pos[s] + np.arange(take[s])
+                pos_new[s * per_seq:(s + 1) * per_seq] = row
+            next_pos += take
+            left -= take
+            select_compact(pos_new, chunk, ki.chunk_inputs(w, chunk, "cpu", t, c), None, f"turn {t} chunk {c}")
+            c += 1
+        for dstep in range(decode_per_turn):
+            inp = ki.decode_inputs(w, t * 1000 + dstep)
+            pos_new = np.repeat(next_pos, per_seq).astype(np.int32).reshape(nseg, 1)
+            next_pos += 1
+            q = inp.pop("q")
+            select_compact(pos_new, 1, inp, q, f"turn {t} decode {dstep}")
+    return results

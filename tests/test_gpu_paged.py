@@ -177,3 +177,26 @@ def test_host_side_argument_checks_of_the_paged_calls():
     with pytest.raises(kv.KvtrimError):
         kv.kvtrim_paged_attn(ctx, pc, q, 0, 2, 0.125, out)        # layer range beyond the model
     assert kv.kvtrim_poll_error(ctx) == 0
+
+
+def test_paged_append_skips_segments_whose_position_is_negative():
+    # one sequence of the batch brings a token, the other does not (its rows are padding)
+    w = wl(2, 1, 2, 2, 64)
+    seg_len = (300, 200, 128, 77)
+    c, now = ki.ragged_cache(w, list(seg_len), reserve=1, salt=4)
+    src = kv.Cache.from_dict(c, DEV)
+    ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, max(src.cap, 16 * P))
+    pc = kv.PagedCache(w.nseg, w.head_dim, 16, 8, DEV)
+    keep = torch.ones(src.cap, dtype=torch.uint8, device=DEV)
+    kept = torch.tensor(list(seg_len), dtype=torch.int32, device=DEV)
+    kv.kvtrim_paged_build(ctx, src, keep, kept, pc)
+    inp = {k: v.to(DEV) for k, v in ki.decode_inputs(w, 0).items()}
+    pos_new = torch.tensor([-1, -1, 9000, 9000], dtype=torch.int32, device=DEV)
+    kv.kvtrim_paged_append(ctx, pc, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos_new)
+    assert kv.kvtrim_poll_error(ctx) == 0
+    ph = PagedHost(pc)
+    assert ph.structure_problems() == []
+    assert list(ph.seg_live) == [300, 200, 129, 78]
+    assert list(ph.seg_pages) == [3, 2, 2, 1]                      # the full page of segment 2 made it take a new one
+    idx, counts = ph.ordered_slots()
+    assert ph.pos[idx[300 + 200 + 128]] == 9000 and ph.pos[idx[-1]] == 9000

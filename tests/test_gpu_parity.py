@@ -12,7 +12,7 @@ import torch
 import kvtrim_inputs as ki
 import oracle
 import paper_2605_09649_amd as kv
-from harness import attn_error, compare_caches, device_cache_to_host, run_steps_both
+from harness import attn_error, compare_caches, device_cache_to_host, run_multiturn_both, run_steps_both
 from helpers import bf16_bits, host_cache, live_mask
 
 pytestmark = pytest.mark.gpu
@@ -63,6 +63,32 @@ def test_ragged_segments_spanning_several_chunks(S, L, H, G, D, fused):
     per_seq = [int(seg_len[s * L * H:(s + 1) * L * H].sum()) for s in range(S)]
     budget = [max(1, n // 3) for n in per_seq]
     check(run_steps_both(w, steps=2, budget=budget, device=DEV, cache_dict=c, now0=now.numpy(), fused=fused))
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_multi_turn_chunked_prefill_then_decode(fused):
+    # the multi-turn configuration scaled down: sequences of different lengths grow by prefill chunks (ragged last
+    # chunks are padded with negative positions), the cache is rescored, selected and compacted after every chunk,
+    # then a few tokens are decoded; four turns, per-sequence budgets
+    w = wl(3, 2, 2, 2, 64)
+    lengths = [700, 180, 411]
+    res = run_multiturn_both(w, lengths, chunk=64, decode_per_turn=3, budget=[160, 10 ** 6, 96], device=DEV, fused=fused)
+    assert len(res) > 20 and any("decode" in r["what"] for r in res)
+    for r in res:
+        assert r["status"] == 0 and r["score_equal"] and r["keep_equal"] and r["cache_equal"], r
+        if "attn_err" in r:
+            assert r["attn_err"] <= ATTN_TOL and r["lse_err"] <= 2e-3, r
+
+
+def test_multi_turn_chunked_sixteen_sequences():
+    w = ki.workload("multiturn", prefill=1024)                   # S16 L32 Hkv8 Hq32 D128, lengths in [64, 1024]
+    per_head = 96
+    res = run_multiturn_both(w, list(w.prefill), chunk=256, decode_per_turn=2, budget=[per_head * 32 * 8] * 16, device=DEV,
+                             turns=2)
+    for r in res:
+        assert r["status"] == 0 and r["score_equal"] and r["keep_equal"] and r["cache_equal"], r
+        if "attn_err" in r:
+            assert r["attn_err"] <= ATTN_TOL and r["lse_err"] <= 2e-3, r
 
 
 @pytest.mark.parametrize("fused", [False, True])

@@ -288,3 +288,22 @@ def test_occupancy_closed_forms():
                 e = hc2.seg_start[g] + j
                 tot += math.exp(float(now2[s] - hc2.pos[e]) * float(hc2.log_beta[e]))
         assert math.isclose(occ2[s], tot, rel_tol=1e-12)
+
+
+def test_append_takes_rows_up_to_the_first_padding_row():
+    # sequences of a batch may bring different numbers of tokens: rows from the first negative position on are padding
+    sh = oracle.Shape(2, 1, 2, 2, 4)
+    hc = oracle.HostCache(sh, 64)
+    hc.seg_start[:] = [0, 16, 32, 48]
+    rng = np.random.default_rng(3)
+    k = rng.integers(0, 60000, (4, 5, 4)).astype(np.uint16)
+    v = rng.integers(0, 60000, (4, 5, 4)).astype(np.uint16)
+    lb = -rng.random((4, 5)).astype(np.float32)
+    pos = np.array([[0, 1, 2, 3, 4], [0, 1, 2, 3, 4], [0, 1, -1, 7, 8], [-1, 0, 1, 2, 3]], np.int32)
+    oracle.append(hc, k, v, lb, pos)
+    assert list(hc.seg_len) == [5, 5, 2, 0]
+    for g, n in enumerate(hc.seg_len):
+        s0 = hc.seg_start[g]
+        assert np.array_equal(hc.k[s0:s0 + n], k[g, :n]) and np.array_equal(hc.v[s0:s0 + n], v[g, :n])
+        assert np.array_equal(hc.log_beta[s0:s0 + n], lb[g, :n]) and np.array_equal(hc.pos[s0:s0 + n], pos[g, :n])
+    assert not hc.k[34:48].any() and not hc.k[48:].any()          # nothing written behind the taken rows
