@@ -214,7 +214,7 @@ kvtrim_status kvtrim_append(kvtrim_ctx *ctx, kvtrim_cache *c, const void *k_new,
  * Slot s of page p is entry p*KVTRIM_PAGE_SIZE + s of the flat score / keep arrays.
  * n_pages * KVTRIM_PAGE_SIZE must not exceed the context's max_entries, and the calls that run
  * attention need n_pages / 4 + nseg to fit the context's partial-result buffer (always true
- * when n_pages <= 131072). */
+ * when n_pages <= 2097152). */
 #define KVTRIM_PAGE_SIZE 128
 typedef struct {
     void *k;

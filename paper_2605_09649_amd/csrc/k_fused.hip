@@ -295,9 +295,12 @@ kvtrim_status launch_compact_attn(kvtrim_ctx* ctx, const CacheView& src, const u
     const Shape& sh = ctx->shape;
     const Workspace& ws = ctx->ws;
     const int64_t max_chunks = src.cap / CMP_CHUNK + sh.nseg;
-    if (max_chunks > ws.max_att_chunks) {
-        // Too many source chunks for the partial-result buffer (a first eviction from a long
-        // prefill): run the two stages one after the other, which computes the same thing.
+    if (max_chunks > ws.max_att_chunks || dst.cap < src.cap / 4) {
+        // Run the two stages one after the other, which computes the same thing: when there are too many source
+        // chunks for the partial-result buffer, and when the destination is so much smaller than the source that
+        // few rows can survive (the first eviction after a long prefill: the fused kernel would launch one block
+        // and write one partial result per 128 source entries for a handful of survivors each - measured 5.4 ms
+        // against 3.0 ms for the two calls at 1 survivor in 16).
         kvtrim_status rc = launch_compact(ctx, src, keep, kept, dst, reserve, st);
         if (rc != KVTRIM_OK) return rc;
         CacheView d;

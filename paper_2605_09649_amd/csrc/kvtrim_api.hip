@@ -53,8 +53,9 @@ static Layout layout_of(const kvtrim_config* c) {
     // the attention chunk grows with the capacity (att_chunk_for) so that at most 16384 full
     // chunks plus one ragged tail per segment ever exist
     // (the fused stage 3+4 kernel also writes one partial result per 128-entry compaction chunk;
-    // it is used for caches of up to 32768 such chunks, larger ones take the two-call path)
-    const int64_t full = c->max_entries / CMP_CHUNK < 32768 ? c->max_entries / CMP_CHUNK : 32768;
+    // it is used for caches of up to 524288 such chunks = 67 M entries, larger ones take the two-call path;
+    // the buffer is [chunk][G][D + 2] fp32, 2 KB per chunk at G = 4, D = 128)
+    const int64_t full = c->max_entries / CMP_CHUNK < 524288 ? c->max_entries / CMP_CHUNK : 524288;
     const int64_t att = full + nseg + 1;
     l.max_att_chunks = att;
     size_t cur = 0;
