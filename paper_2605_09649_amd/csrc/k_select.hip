@@ -98,15 +98,39 @@ __global__ __launch_bounds__(HIST_THREADS) void k_sel_hist(const float* __restri
                 __syncthreads();
                 if (tid < nt) s_desc[tid] = tb.desc[t0 + tid];
                 __syncthreads();
+                if (PAGED) {
+                    // pages are whole, 16-byte aligned chunks: four slots per load
+#pragma unroll 4
+                    for (int s4 = tid; s4 < (nt << (SHIFT - 2)); s4 += HIST_THREADS) {
+                        const ChunkDesc d = s_desc[s4 >> (SHIFT - 2)];
+                        const int64_t e = d.first + ((s4 & ((1 << (SHIFT - 2)) - 1)) << 2);
+                        const float4 sc = *reinterpret_cast<const float4*>(score + e);
+                        const float v[4] = {sc.x, sc.y, sc.z, sc.w};
+                        int bin[4];
+                        bool hit[4];
+                        bool any = false;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            hit[i] = digit_of<PASS>(key_of_score(v[i]), prefix, &bin[i]);
+                            any |= hit[i];
+                        }
+                        if (any) {                                // the positions are looked at only where a prefix matches
+                            const int4 ps = *reinterpret_cast<const int4*>(tb.pos + e);
+                            const int p[4] = {ps.x, ps.y, ps.z, ps.w};
+#pragma unroll
+                            for (int i = 0; i < 4; ++i)
+                                if (hit[i] && p[i] >= 0) atomicAdd(&h[bin[i]], 1u);
+                        }
+                    }
+                } else {
 #pragma unroll 8
-                for (int slot = tid; slot < (nt << SHIFT); slot += HIST_THREADS) {
-                    const ChunkDesc d = s_desc[slot >> SHIFT];
-                    const int j = slot & ((1 << SHIFT) - 1);
-                    if (j < d.n) {                                // the position is looked at only where the prefix matches
-                        int bin;
-                        if (digit_of<PASS>(key_of_score(score[d.first + j]), prefix, &bin) &&
-                            (!PAGED || tb.pos[d.first + j] >= 0))
-                            atomicAdd(&h[bin], 1u);
+                    for (int slot = tid; slot < (nt << SHIFT); slot += HIST_THREADS) {
+                        const ChunkDesc d = s_desc[slot >> SHIFT];
+                        const int j = slot & ((1 << SHIFT) - 1);
+                        if (j < d.n) {
+                            int bin;
+                            if (digit_of<PASS>(key_of_score(score[d.first + j]), prefix, &bin)) atomicAdd(&h[bin], 1u);
+                        }
                     }
                 }
             }
