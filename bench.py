@@ -23,7 +23,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 CPU_STEPS = 16                 # steps the CPU oracle replays after the timed region (a few seconds of host work)
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs, scaled by a plain copy kernel; None until measured for this workload.
-MEASURED_TRAFFIC = {("long", "k_cmp_attn"): 1.1052e9 + 1.1259e9, ("long", "k_cmp_copy"): None}
+MEASURED_TRAFFIC = {("long", "k_cmp_attn"): 1.1052e9 + 1.1259e9, ("long", "k_cmp_copy"): None,
+                    ("long-paged", "k_att_partial"): 1.0942e9 + 8.8e6, ("gate-1", "k_gate_hidden"): 136.5e6 + 65.5e3}
 
 
 def log(*a):
@@ -88,7 +89,8 @@ def bench_gate(args):
     flops_hidden = 2.0 * n_tok * L * dg * dm
     if n_tok <= 64:
         roof = {"bound": "hbm", "kernel": "k_gate_hidden", "achieved": alg_hidden / (h_ms * 1e-3) / 1e9,
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": None, "algorithmic_bytes_per_launch": alg_hidden}
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": MEASURED_TRAFFIC.get((f"gate-{n_tok}", "k_gate_hidden")),
+                "algorithmic_bytes_per_launch": alg_hidden}
     else:
         roof = {"bound": "mfma", "kernel": "k_gate_hidden", "achieved": flops_hidden / (h_ms * 1e-3) / 1e12,
                 "peak": 2500.0, "unit": "TFLOP/s", "traffic": None, "flops_per_launch": flops_hidden}
@@ -348,7 +350,8 @@ def main():
                        "frac_of_hbm_peak": alg_total / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
                        "bytes_by_stage": alg},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get((w.name, dom)),
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC.get((w.name + ("-paged" if args.paged else ""), dom)),
                      "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_avg_ms, "launches": dom_n,
                      "stage_model_bytes_per_launch": stage_model_bytes,
                      "stage_model_achieved": (stage_model_bytes / (dom_avg_ms * 1e-3) / 1e9) if stage_model_bytes else None,
