@@ -47,3 +47,14 @@ def test_product_path_does_not_reach_the_oracle():
             if f.endswith((".py", ".hip", ".h")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.replace("no CPU fallback", ""), f
+
+
+def test_entry_limit_and_kernel_name_table():
+    assert kv.kvtrim_workspace_bytes(1, 1, 1, 1, 64, 2 ** 31 - 4096) > 0
+    assert kv.kvtrim_workspace_bytes(1, 1, 1, 1, 64, 2 ** 31 - 4095) == 0   # segment entries are indexed with 32-bit integers
+    names = [kv.kvtrim_kernel_name(i) for i in range(kv.binding.N_KERNELS)]
+    assert all(names) and len(set(names)) == len(names)
+    assert kv.kvtrim_kernel_name(kv.binding.N_KERNELS) is None and kv.kvtrim_kernel_name(-1) is None
+    header = open(os.path.join(ROOT, "include", "kvtrim.h")).read()
+    assert f"#define KVTRIM_N_KERNELS {kv.binding.N_KERNELS}" in header
+    assert f"#define KVTRIM_PAGE_SIZE {kv.PAGE_SIZE}" in header
