@@ -283,9 +283,9 @@ static bool dispatch_fused(int G, dim3 grid, hipStream_t st, const CacheView& sr
     switch (G) {
 #define KVTRIM_CASE(g) \
     case g: hipLaunchKernelGGL((k_cmp_attn<D, g>), grid, dim3(FUS_THREADS), 0, st, src, keep, dst, q, sh, ws, scale_log2, lb, le); return true;
-        KVTRIM_CASE(1) KVTRIM_CASE(2) KVTRIM_CASE(3) KVTRIM_CASE(4) KVTRIM_CASE(5) KVTRIM_CASE(6) KVTRIM_CASE(7) KVTRIM_CASE(8)
+        KVTRIM_CASE(1) KVTRIM_CASE(2) KVTRIM_CASE(3) KVTRIM_CASE(4) KVTRIM_CASE(5) KVTRIM_CASE(6)
 #undef KVTRIM_CASE
-        default: return false;
+        default: return false;                                    // larger groups take the two-call path
     }
 }
 
@@ -295,12 +295,19 @@ kvtrim_status launch_compact_attn(kvtrim_ctx* ctx, const CacheView& src, const u
     const Shape& sh = ctx->shape;
     const Workspace& ws = ctx->ws;
     const int64_t max_chunks = src.cap / CMP_CHUNK + sh.nseg;
-    if (max_chunks > ws.max_att_chunks || dst.cap < src.cap / 4) {
+    // The fused kernel does q.k and p.v on the vector ALU with G query heads' worth of accumulators per lane: it
+    // stays bound by HBM up to G = 6 at head_dim 128 and G = 5 at head_dim 64 (2.1 M retained entries, head_dim
+    // 128: 363-440 us for G = 1..6 against 553-569 us for the two calls, but 804 / 863 us at G = 7 / 8, where the
+    // accumulators no longer fit the register file; head_dim 64: 183-254 us for G = 1..5 against 275-279 us, 292
+    // against 281 us at G = 6).  Above that the copy kernel plus the MFMA attention kernel are faster.
+    const bool alu_fits = sh.head_dim == 128 ? sh.group <= 6 : sh.group <= 5;
+    if (max_chunks > ws.max_att_chunks || dst.cap < src.cap / 4 || !alu_fits) {
         // Run the two stages one after the other, which computes the same thing: when there are too many source
-        // chunks for the partial-result buffer, and when the destination is so much smaller than the source that
-        // few rows can survive (the first eviction after a long prefill: the fused kernel would launch one block
-        // and write one partial result per 128 source entries for a handful of survivors each - measured 5.4 ms
-        // against 3.0 ms for the two calls at 1 survivor in 16).
+        // chunks for the partial-result buffer, when the group of query heads is too large (above), and when the
+        // destination is so much smaller than the source that few rows can survive (the first eviction after a
+        // long prefill: the fused kernel would launch one block and write one partial result per 128 source
+        // entries for a handful of survivors each - measured 5.4 ms against 3.0 ms for the two calls at 1
+        // survivor in 16).
         kvtrim_status rc = launch_compact(ctx, src, keep, kept, dst, reserve, st);
         if (rc != KVTRIM_OK) return rc;
         CacheView d;
