@@ -147,6 +147,9 @@ def main():
     ap.add_argument("--kernel-times", action="store_true",
                     help="bracket every kernel with HIP events and print the per-kernel averages to stderr "
                          "(the events add a little to ms_per_step)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the K timed steps into one HIP graph and time its replay (the per-kernel figures "
+                         "then come from 20 eager steps run just before)")
     ap.add_argument("--gate", type=int, default=0, metavar="N_TOK",
                     help="time the retention-gate forward alone (the metric model's shape: 32 layers x 8 KV heads, "
                          "d_model 4096, hidden width 512, projection width 128) for N_TOK tokens per call")
@@ -172,7 +175,8 @@ def main():
     w = ki.workload(args.workload, prefill=args.prefill)
     reserve = 1
     K, W = args.steps, max(args.warmup, 1)
-    n_steps = K + W + CPU_STEPS               # + the extra steps that are replayed on the CPU oracle
+    G_STEPS = 20 if args.graph else 0         # eager, profiled steps before a captured region
+    n_steps = K + W + G_STEPS + CPU_STEPS     # + the extra steps that are replayed on the CPU oracle
 
     t0 = time.time()
     pre = ki.with_horizon(ki.prefill_cache(w, reserve=reserve, device=dev), args.horizon)
@@ -277,12 +281,27 @@ def main():
         mask = (1 << kv.binding.N_KERNELS) - 1   # every kernel (the events then add to the step time)
     kv.kvtrim_profile_begin(ctx, mask)
     torch.cuda.synchronize()
-    t_begin = time.perf_counter()
-    for s in range(W, W + K):
-        step(s)
-    torch.cuda.synchronize()
-    t_end = time.perf_counter()
-    prof = kv.kvtrim_profile_end(ctx)
+    if args.graph:
+        for s in range(W, W + G_STEPS):       # per-kernel durations: events cannot be recorded inside a capture
+            step(s)
+        torch.cuda.synchronize()
+        prof = kv.kvtrim_profile_end(ctx)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):         # the library only enqueues kernels on the current stream
+            for s in range(W + G_STEPS, W + G_STEPS + K):
+                step(s)
+        torch.cuda.synchronize()
+        t_begin = time.perf_counter()
+        graph.replay()
+        torch.cuda.synchronize()
+        t_end = time.perf_counter()
+    else:
+        t_begin = time.perf_counter()
+        for s in range(W, W + K):
+            step(s)
+        torch.cuda.synchronize()
+        t_end = time.perf_counter()
+        prof = kv.kvtrim_profile_end(ctx)
     assert kv.kvtrim_poll_error(ctx) == 0, "device-side error in the timed region"
     if args.kernel_times:
         for name, (ms, n) in sorted(prof.items(), key=lambda kvp: -kvp[1][0]):
@@ -345,6 +364,7 @@ def main():
                        "append, score, select_global, compact, decode_attn (five C-ABI calls per step)" if args.unfused else
                        "append, score, select_global, compact_attn (stages 3+4 fused; four C-ABI calls per step)"),
             "first_step_ms": first_ms,
+            "launch": "one HIP graph holding the K timed steps, replayed once" if args.graph else "eager launches",
         },
         "end_to_end": {"algorithmic_bytes_per_step": alg_total, "achieved_GBps": alg_total / (ms_per_step * 1e-3) / 1e9,
                        "frac_of_hbm_peak": alg_total / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
@@ -378,7 +398,7 @@ def main():
             hc = device_cache_to_host(w, state["src"])
         budget_np = np.array(list(w.budget), np.int64)
         cpu_s, ok_sel, err = 0.0, True, 0.0
-        for s in range(W + K, W + K + CPU_STEPS):
+        for s in range(W + G_STEPS + K, W + G_STEPS + K + CPU_STEPS):
             inp = {k: v.cpu() for k, v in inputs[s].items()}
             now = now0 + s + 1
             pos_new = np.repeat(now, per_seq).astype(np.int32)
