@@ -364,7 +364,8 @@ __global__ __launch_bounds__(1024) void k_pg_plan(PagedView pc, Shape sh, const 
         st.tie_quota = 0;
         st.keep_none = st.want == 0;
         st.need_rank = 0;
-        ws.sel[seq] = st;
+        ws.sel[seq] = st;                                            // final slot (what the count and mask kernels read)
+        ws.sel[sh.n_seq + seq] = st;                                 // state before the first digit
         if (thr_out) thr_out[seq] = 0xFFFFFFFFu;
     }
 }

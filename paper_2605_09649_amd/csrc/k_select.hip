@@ -55,8 +55,54 @@ __global__ __launch_bounds__(1024) void k_sel_plan(CacheView c, Shape sh, const 
         st.tie_quota = 0;
         st.keep_none = st.want == 0;
         st.need_rank = 0;
-        ws.sel[seq] = st;
+        ws.sel[seq] = st;                                         // final slot (what the count and mask kernels read)
+        ws.sel[sh.n_seq + seq] = st;                              // state before the first digit
     }
+}
+
+// One digit of the threshold key: walks the merged histogram of pass P (the sum of its replicas) of sequence
+// `seq` from the top bin down to the bin that holds the entry of rank st.rank (1-based, descending key order)
+// and returns the state with that digit appended.  Called by all threads of a 1024-thread block; `cnt_out`
+// gets the population of the chosen bin.
+template <int P>
+__device__ __forceinline__ SelState next_digit(const uint32_t* __restrict__ hist_pass, int n_seq, int seq, SelState st,
+                                               int64_t* lds64, SelState* s_state, uint32_t* cnt_out) {
+    constexpr int NB = P == 2 ? 1024 : 2048;
+    constexpr int PER = NB / 1024;                                // bins per thread (1 or 2), thread 0 owns the highest bins
+    const int tid = threadIdx.x;
+    uint32_t cnt[PER];
+    int64_t mine = 0;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int bin = NB - 1 - (tid * PER + i);
+        uint32_t v = 0;
+#pragma unroll
+        for (int r = 0; r < HIST_REPLICAS; ++r) v += hist_pass[((size_t)r * n_seq + seq) * RADIX_BINS + bin];
+        cnt[i] = v;
+        mine += v;
+    }
+    int64_t tot;
+    int64_t above = block_excl_scan<int64_t>(mine, lds64, &tot);
+    if (above < st.rank && st.rank <= above + mine) {
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            if (st.rank <= above + cnt[i]) {
+                const uint32_t bin = NB - 1 - (tid * PER + i);
+                const int bits = P == 2 ? RADIX_BITS2 : (P == 1 ? RADIX_BITS1 : RADIX_BITS0);
+                SelState o = st;
+                o.prefix = (st.prefix << bits) | bin;
+                o.rank = st.rank - above;
+                *s_state = o;
+                *cnt_out = cnt[i];
+                break;
+            }
+            above += cnt[i];
+        }
+    }
+    __syncthreads();
+    const SelState o = *s_state;
+    __syncthreads();                                              // s_state may be written again by the next call
+    return o;
 }
 
 // Histogram of the next digit over the entries whose higher digits equal the prefix found so
@@ -75,6 +121,8 @@ __global__ __launch_bounds__(HIST_THREADS) void k_sel_hist(const float* __restri
     __shared__ uint32_t h[NB];
     __shared__ ChunkDesc s_desc[HIST_TILE];
     __shared__ int64_t lds64[17];
+    __shared__ SelState s_state;
+    __shared__ uint32_t s_cnt;
     __shared__ int is_last;
     const int tid = threadIdx.x;
     const int4 rng = ws.sel_blk[blockIdx.x];
@@ -89,8 +137,19 @@ __global__ __launch_bounds__(HIST_THREADS) void k_sel_hist(const float* __restri
             const int a = max(c0, tb.prefix[seq * sh.segs_per_seq]);
             const int b = min(c1, tb.prefix[(seq + 1) * sh.segs_per_seq]);
             if (a >= b) continue;
-            const uint32_t prefix = ws.sel[seq].prefix;
             if (ws.sel[seq].keep_none) continue;
+            // The digits fixed so far: every block derives them itself from the previous pass's merged histogram
+            // (a few microseconds of L2 reads, the same for all blocks) instead of waiting for that pass's last
+            // block to do it, which put "last block done" detection and the walk on the critical path of every pass.
+            // (slots of ws.sel: [0] final, [1] after the plan, [2] after the first digit, [3] after the second)
+            SelState st = ws.sel[(size_t)(PASS > 1 ? PASS : 1) * sh.n_seq + seq];
+            if (PASS > 0) {
+                uint32_t unused;
+                st = next_digit<(PASS > 0 ? PASS - 1 : 0)>(ws.hist + (size_t)(PASS - 1) * HIST_REPLICAS * sh.n_seq * RADIX_BINS,
+                                                          sh.n_seq, seq, st, lds64, &s_state, &unused);
+            }
+            if (PASS > 0 && tid == 0) ws.sel[(size_t)(PASS + 1) * sh.n_seq + seq] = st;   // the same value from every block
+            const uint32_t prefix = st.prefix;
             // the descriptors of a tile of chunks go through LDS so that the score loads of a
             // thread do not depend on anything loaded inside the loop and are all in flight at once
             for (int t0 = a; t0 < b; t0 += HIST_TILE) {
@@ -144,55 +203,29 @@ __global__ __launch_bounds__(HIST_THREADS) void k_sel_hist(const float* __restri
             }
         }
     }
+    if (PASS < 2) return;                                         // the next pass finds this pass's digit itself
+
     __syncthreads();
     if (tid == 0) is_last = arrive_last(ws.done + 32 * PASS);
     __syncthreads();
     if (!is_last) return;
     __threadfence();
 
-    // Last block: per sequence, walk the histogram from the top bin down to the bin that
-    // holds the entry of rank `rank` (1-based, in descending key order).
-    constexpr int PER = NB / HIST_THREADS;   // bins per thread (1 or 2), thread 0 owns the highest bins
+    // Last block of the last pass: per sequence the final digit, hence the threshold key, how many of the
+    // entries equal to it survive, and whether those have to be ranked in order.
     for (int seq = 0; seq < sh.n_seq; ++seq) {
-        SelState st = ws.sel[seq];
-        if (st.keep_none) {
-            if (PASS == 2 && tid == 0 && thr_out) thr_out[seq] = 0xFFFFFFFFu;
+        if (ws.sel[seq].keep_none) {
+            if (tid == 0 && thr_out) thr_out[seq] = 0xFFFFFFFFu;
             continue;
         }
-        uint32_t cnt[PER];
-        int64_t mine = 0;
-#pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            const int bin = NB - 1 - (tid * PER + i);
-            uint32_t v = 0;
-#pragma unroll
-            for (int r = 0; r < HIST_REPLICAS; ++r)      // plain loads: the fence above made the other blocks' sums visible
-                v += hist_pass[((size_t)r * sh.n_seq + seq) * RADIX_BINS + bin];
-            cnt[i] = v;
-            mine += v;
-        }
-        int64_t tot;
-        int64_t above = block_excl_scan<int64_t>(mine, lds64, &tot);
-        if (above < st.rank && st.rank <= above + mine) {
-#pragma unroll
-            for (int i = 0; i < PER; ++i) {
-                if (st.rank <= above + cnt[i]) {
-                    const uint32_t bin = NB - 1 - (tid * PER + i);
-                    const int bits = PASS == 2 ? RADIX_BITS2 : (PASS == 1 ? RADIX_BITS1 : RADIX_BITS0);
-                    st.prefix = (st.prefix << bits) | bin;
-                    st.rank -= above;
-                    if (PASS == 2) {
-                        st.thr_key = st.prefix;
-                        st.tie_quota = st.rank;
-                        st.need_rank = st.rank < (int64_t)cnt[i];   // fewer survive than tie at the threshold
-                        if (st.need_rank) atomicOr((int*)&ws.done[127], 1);
-                        if (thr_out) thr_out[seq] = st.thr_key;
-                    }
-                    ws.sel[seq] = st;
-                    break;
-                }
-                above += cnt[i];
-            }
+        SelState st = next_digit<2>(hist_pass, sh.n_seq, seq, ws.sel[(size_t)3 * sh.n_seq + seq], lds64, &s_state, &s_cnt);
+        if (tid == 0) {
+            st.thr_key = st.prefix;
+            st.tie_quota = st.rank;
+            st.need_rank = st.rank < (int64_t)s_cnt;              // fewer survive than tie at the threshold
+            if (st.need_rank) atomicOr((int*)&ws.done[127], 1);
+            if (thr_out) thr_out[seq] = st.thr_key;
+            ws.sel[seq] = st;
         }
         __syncthreads();
     }

@@ -62,7 +62,7 @@ static Layout layout_of(const kvtrim_config* c) {
     l.off[0] = bump(cur, (nseg + 1) * sizeof(int32_t));                        // sel_chunk_prefix
     l.off[1] = bump(cur, l.max_sel_chunks * sizeof(ChunkDesc));                // sel_desc
     l.off[2] = bump(cur, (size_t)3 * HIST_REPLICAS * c->n_seq * RADIX_BINS * sizeof(uint32_t)); // hist
-    l.off[3] = bump(cur, (size_t)c->n_seq * sizeof(SelState));                 // sel
+    l.off[3] = bump(cur, (size_t)4 * c->n_seq * sizeof(SelState));             // sel: final state + the state after the plan and after each of the first two passes
     l.off[4] = bump(cur, DONE_WORDS * sizeof(uint32_t));                       // done
     l.off[5] = bump(cur, l.max_sel_chunks * sizeof(int32_t));                  // chunk_eq
     l.off[6] = bump(cur, l.max_sel_chunks * sizeof(int64_t));                  // chunk_tie_base
