@@ -34,6 +34,54 @@ __device__ __forceinline__ void block_sum_n(int64_t (&v)[N], int64_t* lds /* [16
     }
 }
 
+// With many segments the per-block reduction over all segments below costs more than a launch: one block
+// then scans the segments once and leaves, per segment, the first chunk (ws.cmp_chunk_prefix) and the first
+// destination entry (dst.seg_start) - the two values k_cmp_scan would otherwise derive in every block.
+__global__ __launch_bounds__(SCAN_THREADS) void k_cmp_prefix(CacheView src, const int32_t* __restrict__ kept,
+                                                             CacheViewMut dst, int reserve, int align, Shape sh,
+                                                             Workspace ws) {
+    __shared__ int64_t lds64[17];
+    __shared__ int s_bad_layout, s_bad_kept;
+    const int tid = threadIdx.x, nseg = sh.nseg;
+    if (tid == 0) s_bad_layout = s_bad_kept = 0;
+    __syncthreads();
+    int64_t chunks = 0, entries = 0;
+    for (int base = 0; base < nseg; base += SCAN_THREADS) {
+        const int i = base + tid;
+        int64_t nch = 0, need = 0;
+        if (i < nseg) {
+            const int len = src.seg_len[i];
+            const int64_t st = src.seg_start[i];
+            const int kp = kept[i];
+            if (len < 0 || st < 0 || st + len > src.cap) s_bad_layout = 1;
+            if (kp < 0 || kp > len) s_bad_kept = 1;
+            nch = len > 0 ? ((int64_t)len + CMP_CHUNK - 1) / CMP_CHUNK : 0;
+            need = ((int64_t)kp + reserve + align - 1) / align * align;
+        }
+        int64_t tot_c, tot_e;
+        const int64_t ex_c = block_excl_scan<int64_t>(nch, lds64, &tot_c);
+        const int64_t ex_e = block_excl_scan<int64_t>(need, lds64, &tot_e);
+        if (i < nseg) {
+            ws.cmp_chunk_prefix[i] = (int32_t)min(chunks + ex_c, (int64_t)0x7fffffff);
+            dst.seg_start[i] = entries + ex_e;
+        }
+        chunks += tot_c;
+        entries += tot_e;
+    }
+    __syncthreads();
+    const bool bad_layout = s_bad_layout || chunks > ws.max_cmp_chunks, bad_kept = s_bad_kept != 0;
+    if (tid == 0) {
+        if (bad_layout || bad_kept || entries > dst.cap) {
+            atomicOr(ws.err, bad_layout ? ERR_LAYOUT : (bad_kept ? ERR_MISMATCH : ERR_CAP));
+            ws.cmp_chunk_prefix[nseg] = 0;
+        } else {
+            ws.cmp_chunk_prefix[nseg] = (int32_t)chunks;
+        }
+    }
+}
+
+// PRE: k_cmp_prefix has run (segment prefixes and the checks over all segments are done).
+template <bool PRE>
 __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const uint8_t* __restrict__ keep,
                                                            const int32_t* __restrict__ kept, CacheViewMut dst,
                                                            int reserve, int align, Shape sh, Workspace ws) {
@@ -43,32 +91,41 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const 
     const int g = blockIdx.x;
     const int nseg = sh.nseg;
 
-    // chunks and destination entries of the segments before g, and the totals
-    int64_t acc[6] = {0, 0, 0, 0, 0, 0};   // chunks_before, dst_before, dst_total, chunks_total, bad_layout, bad_kept
-    for (int i = tid; i < nseg; i += SCAN_THREADS) {
-        const int len = src.seg_len[i];
-        const int64_t st = src.seg_start[i];
-        const int kp = kept[i];
-        acc[4] |= (len < 0 || st < 0 || st + len > src.cap);
-        acc[5] |= (kp < 0 || kp > len);
-        const int64_t nch = len > 0 ? ((int64_t)len + CMP_CHUNK - 1) / CMP_CHUNK : 0;
-        const int64_t need = ((int64_t)kp + reserve + align - 1) / align * align;   // align = 1 unless pages are built
-        acc[3] += nch;
-        acc[2] += need;
-        if (i < g) {
-            acc[0] += nch;
-            acc[1] += need;
+    int64_t chunks_before, dst_before;
+    if (PRE) {
+        if (__hip_atomic_load(ws.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
+        chunks_before = ws.cmp_chunk_prefix[g];
+        dst_before = dst.seg_start[g];
+    } else {
+        // chunks and destination entries of the segments before g, and the totals
+        int64_t acc[6] = {0, 0, 0, 0, 0, 0};   // chunks_before, dst_before, dst_total, chunks_total, bad_layout, bad_kept
+        for (int i = tid; i < nseg; i += SCAN_THREADS) {
+            const int len = src.seg_len[i];
+            const int64_t st = src.seg_start[i];
+            const int kp = kept[i];
+            acc[4] |= (len < 0 || st < 0 || st + len > src.cap);
+            acc[5] |= (kp < 0 || kp > len);
+            const int64_t nch = len > 0 ? ((int64_t)len + CMP_CHUNK - 1) / CMP_CHUNK : 0;
+            const int64_t need = ((int64_t)kp + reserve + align - 1) / align * align;   // align = 1 unless pages are built
+            acc[3] += nch;
+            acc[2] += need;
+            if (i < g) {
+                acc[0] += nch;
+                acc[1] += need;
+            }
         }
-    }
-    block_sum_n<6>(acc, lds_n);
-    const int64_t chunks_before = acc[0], dst_before = acc[1], dst_total = acc[2], chunks_total = acc[3];
-    const bool bad_layout = acc[4] != 0 || chunks_total > ws.max_cmp_chunks, bad_kept = acc[5] != 0;
-    if (bad_layout || bad_kept || dst_total > dst.cap) {       // every block takes the same decision
-        if (tid == 0) {
-            atomicOr(ws.err, bad_layout ? ERR_LAYOUT : (bad_kept ? ERR_MISMATCH : ERR_CAP));
-            if (g == 0) ws.cmp_chunk_prefix[nseg] = 0;
+        block_sum_n<6>(acc, lds_n);
+        chunks_before = acc[0];
+        dst_before = acc[1];
+        const int64_t dst_total = acc[2], chunks_total = acc[3];
+        const bool bad_layout = acc[4] != 0 || chunks_total > ws.max_cmp_chunks, bad_kept = acc[5] != 0;
+        if (bad_layout || bad_kept || dst_total > dst.cap) {       // every block takes the same decision
+            if (tid == 0) {
+                atomicOr(ws.err, bad_layout ? ERR_LAYOUT : (bad_kept ? ERR_MISMATCH : ERR_CAP));
+                if (g == 0) ws.cmp_chunk_prefix[nseg] = 0;
+            }
+            return;
         }
-        return;
     }
 
     const int len = src.seg_len[g];
@@ -110,8 +167,10 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const 
         if (running != kept[g]) atomicOr(ws.err, ERR_MISMATCH);
         dst.seg_start[g] = dst_before;
         dst.seg_len[g] = kept[g];
-        ws.cmp_chunk_prefix[g] = cbase;
-        if (g == nseg - 1) ws.cmp_chunk_prefix[nseg] = cbase + nch;
+        if (!PRE) {
+            ws.cmp_chunk_prefix[g] = cbase;
+            if (g == nseg - 1) ws.cmp_chunk_prefix[nseg] = cbase + nch;
+        }
     }
 }
 
@@ -194,8 +253,14 @@ __global__ __launch_bounds__(CMP_THREADS) void k_cmp_copy(CacheView src, const u
 void launch_cmp_scan_aligned(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const int32_t* kept,
                              const CacheViewMut& dst, int32_t reserve, int32_t align, hipStream_t st) {
     ProfScope prof(ctx, K_CMP_SCAN, st);
-    hipLaunchKernelGGL(k_cmp_scan, dim3(ctx->shape.nseg), dim3(SCAN_THREADS), 0, st, src, keep, kept, dst, reserve,
-                       align, ctx->shape, ctx->ws);
+    if (ctx->shape.nseg > 1024) {                                 // see k_cmp_prefix
+        hipLaunchKernelGGL(k_cmp_prefix, dim3(1), dim3(SCAN_THREADS), 0, st, src, kept, dst, reserve, align, ctx->shape, ctx->ws);
+        hipLaunchKernelGGL(k_cmp_scan<true>, dim3(ctx->shape.nseg), dim3(SCAN_THREADS), 0, st, src, keep, kept, dst, reserve,
+                           align, ctx->shape, ctx->ws);
+    } else {
+        hipLaunchKernelGGL(k_cmp_scan<false>, dim3(ctx->shape.nseg), dim3(SCAN_THREADS), 0, st, src, keep, kept, dst, reserve,
+                           align, ctx->shape, ctx->ws);
+    }
 }
 
 void launch_cmp_scan(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const int32_t* kept,

@@ -398,3 +398,31 @@ def test_soft_retention_gated_attention_and_occupancy(D, G, S):
     occ = torch.zeros(S, dtype=torch.float64, device=DEV)
     kv.kvtrim_occupancy(ctx, dc, now_dev, occ)
     np.testing.assert_allclose(occ.cpu().numpy(), oracle.occupancy(hc, now_np), rtol=2e-6)
+
+
+def test_many_segments_take_the_prefix_kernel_and_report_errors():
+    # more than 1024 segments: the segment prefixes of the compaction come from one extra block instead of a
+    # reduction in every block; results and device-side errors must be the same
+    w = wl(9, 8, 16, 1, 64)                                        # 1152 segments
+    rng = np.random.default_rng(77)
+    seg_len = rng.integers(0, 40, w.nseg)
+    c, now = ki.ragged_cache(w, seg_len, reserve=1, salt=8)
+    per_seq = [int(seg_len[s * 128:(s + 1) * 128].sum()) for s in range(9)]
+    check(run_steps_both(w, steps=2, budget=[max(1, n // 2) for n in per_seq], device=DEV, cache_dict=c, now0=now.numpy(),
+                         fused=True))
+    hc = host_cache(w, c)
+    ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, hc.cap)
+    src = kv.Cache.from_dict(c, DEV)
+    keep = torch.ones(hc.cap, dtype=torch.uint8, device=DEV)
+    kept = torch.from_numpy(hc.seg_len.copy()).to(DEV)
+    small = kv.Cache.empty(w.nseg, w.head_dim, int(hc.seg_len.sum()) // 2, DEV)
+    kv.kvtrim_compact(ctx, src, keep, kept, small, 0)
+    assert kv.kvtrim_poll_error(ctx) == -4                         # destination too small
+    roomy = kv.Cache.empty(w.nseg, w.head_dim, hc.cap, DEV)
+    kept[5] += 1
+    kv.kvtrim_compact(ctx, src, keep, kept, roomy, 0)
+    assert kv.kvtrim_poll_error(ctx) == -5                         # kept disagrees with the mask
+    kept[5] -= 1
+    kv.kvtrim_compact(ctx, src, keep, kept, roomy, 0)
+    assert kv.kvtrim_poll_error(ctx) == 0
+    assert compare_caches(device_cache_to_host(w, roomy), oracle.compact(hc, np.ones(hc.cap, np.uint8), hc.cap, 0))
