@@ -169,8 +169,10 @@ kvtrim_status kvtrim_occupancy(kvtrim_ctx *ctx, const kvtrim_cache *c, const int
 /* Stages 3 + 4 fused: exactly kvtrim_compact(src -> dst) followed by
  * kvtrim_decode_attn(dst), with the same arguments, results and device-side errors,
  * but every surviving K/V row is read from HBM once: it is used for the attention of
- * its segment while it is moved.  (When the source cache is too large for the
- * partial-result buffer of the context the two stages simply run one after the other.) */
+ * its segment while it is moved.  The library runs the two stages one after the other
+ * instead - same results - where the fused kernel would not pay: more than 6 query heads
+ * per KV head (5 at head_dim 64), a destination of less than a quarter of the source's
+ * capacity (few rows can survive), or a source of more than 67 M entries. */
 kvtrim_status kvtrim_compact_attn(kvtrim_ctx *ctx, const kvtrim_cache *src, const uint8_t *keep,
                                   const int32_t *kept, kvtrim_cache *dst, int32_t reserve, const void *q,
                                   int32_t layer_begin, int32_t layer_end, float softmax_scale, float *out,
