@@ -1,0 +1,62 @@
+"""Seeded sweep over small random configurations: shapes, ragged and empty segments, budgets from 0 to above
+the entry count, quantised log beta (exact score ties everywhere) - the ragged loop (two-call and fused) and the
+paged loop against the oracle, every stage compared as in the other parity tests."""
+import numpy as np
+import pytest
+import torch
+
+import kvtrim_inputs as ki
+from harness import run_steps_both
+from paged_harness import run_paged_both
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+ATTN_TOL = 5e-3
+
+
+def random_case(seed):
+    rng = np.random.default_rng(1000 + seed)
+    S = int(rng.integers(1, 4))
+    L = int(rng.integers(1, 4))
+    H = int(rng.integers(1, 4))
+    G = int(rng.integers(1, 9))
+    D = int(rng.choice([64, 128]))
+    w = ki.Workload("r", 0, S, L, H, G * H, D, (0,) * S, (0,) * S, 1, 3.0, 1.5)
+    hi = int(rng.choice([5, 150, 700, 2600]))
+    seg_len = rng.integers(0, hi + 1, w.nseg)
+    seg_len[rng.random(w.nseg) < 0.2] = 0
+    c, now = ki.ragged_cache(w, seg_len, reserve=1, salt=seed, pos_stride_max=int(rng.integers(1, 5)))
+    if rng.random() < 0.5:                                         # few distinct retention values: ties at the threshold
+        g = torch.Generator().manual_seed(seed)
+        levels = int(rng.choice([1, 2, 7]))
+        q = torch.randint(0, levels, c["log_beta"].shape, generator=g)
+        c["log_beta"] = -(q.to(torch.float32)) * 0.25
+    per_seq = [int(seg_len[s * L * H:(s + 1) * L * H].sum()) for s in range(S)]
+    steps = int(rng.integers(2, 5))
+    budgets = []
+    for _ in range(steps):
+        b = []
+        for n in per_seq:
+            kind = rng.random()
+            b.append(0 if kind < 0.1 else (10 ** 6 if kind < 0.2 else int(rng.integers(1, max(2, n + 10)))))
+        budgets.append(b)
+    return w, c, now, budgets
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_random_configuration(seed):
+    w, c, now, budgets = random_case(seed)
+    clone = lambda: {k: (v.clone() if torch.is_tensor(v) else v) for k, v in c.items()}
+    for fused in (False, True):
+        # the ragged harness takes one budget for all steps: the first of the list
+        res = run_steps_both(w, steps=len(budgets), budget=budgets[0], device=DEV, cache_dict=clone(), now0=now.numpy(),
+                             fused=fused)
+        for i, r in enumerate(res):
+            assert r["status"] == 0 and r["score_equal"] and r["keep_equal"] and r["cache_equal"], (seed, fused, i, r)
+            assert r["attn_err"] <= ATTN_TOL and r["lse_err"] <= 2e-3 and r["lse_inf_equal"], (seed, fused, i, r)
+    res = run_paged_both(w, budgets, device=DEV, cache_dict=clone(), now0=now.numpy())
+    for r in res:
+        assert r["status"] == 0 and r.get("status_select", 0) == 0, (seed, r)
+        assert r["structure"] == [] and r.get("structure_pre", []) == [], (seed, r)
+        assert r["score_equal"] and r["keep_equal"] and r["kept_equal"] and r["cache_equal"], (seed, r)
+        assert r["attn_err"] <= ATTN_TOL and r["lse_err"] <= 2e-3 and r["lse_inf_equal"], (seed, r)
