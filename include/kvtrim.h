@@ -243,14 +243,15 @@ typedef struct {
 kvtrim_status kvtrim_paged_build(kvtrim_ctx *ctx, const kvtrim_cache *src, const uint8_t *keep,
                                  const int32_t *kept, kvtrim_paged_cache *dst, void *hip_stream);
 
-/* One new token per segment (k_new, v_new: bf16 [nseg][head_dim]; log_beta_new, pos_new:
- * [nseg]; log_tail_new iff the cache carries log_tail; a negative position = no token for
- * that segment): it takes an empty slot of the segment's pages, or the first slot of a page
- * from the free list.  KVTRIM_ECAP when no page is
- * free or the block table is full (that segment is then left unchanged). */
+/* New tokens enter the pages: up to n_new (1 .. 4096) per segment, laid out as for kvtrim_append
+ * (k_new, v_new: bf16 [nseg][n_new][head_dim]; log_beta_new, pos_new: [nseg][n_new]; log_tail_new
+ * iff the cache carries log_tail; a segment takes its rows up to the first negative position, the
+ * rest is padding).  Tokens take the empty slots of the segment's pages first, then pages from the
+ * free list.  KVTRIM_ECAP when the free list or the block table cannot hold a segment's tokens
+ * (that segment is then left unchanged). */
 kvtrim_status kvtrim_paged_append(kvtrim_ctx *ctx, kvtrim_paged_cache *c, const void *k_new, const void *v_new,
                                   const float *log_beta_new, const float *log_tail_new, const int32_t *pos_new,
-                                  void *hip_stream);
+                                  int32_t n_new, void *hip_stream);
 
 /* Stage 1 on the paged layout: score_out fp32 [n_pages * KVTRIM_PAGE_SIZE]; the slots of every
  * segment's pages are written (0 for empty slots), free pages are left alone. */

@@ -88,7 +88,7 @@ def load_library():
         P = C.POINTER(_PagedCache)
         lib.kvtrim_paged_build.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_void_p, P, C.c_void_p]
         lib.kvtrim_paged_append.argtypes = [C.c_void_p, P, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
-                                            C.c_void_p]
+                                            C.c_int32, C.c_void_p]
         lib.kvtrim_paged_score.argtypes = [C.c_void_p, P, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.kvtrim_paged_select.argtypes = [C.c_void_p, P, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                             C.c_void_p]
@@ -311,11 +311,11 @@ def kvtrim_paged_build(ctx, src, keep, kept, dst, stream=None):
            "kvtrim_paged_build")
 
 
-def kvtrim_paged_append(ctx, cache, k_new, v_new, log_beta_new, pos_new, log_tail_new=None, stream=None):
+def kvtrim_paged_append(ctx, cache, k_new, v_new, log_beta_new, pos_new, log_tail_new=None, n_new=1, stream=None):
     _check(ctx, load_library().kvtrim_paged_append(
         ctx.handle, C.byref(cache.c), _ptr(k_new, torch.bfloat16), _ptr(v_new, torch.bfloat16),
         _ptr(log_beta_new, torch.float32), _ptr(log_tail_new, torch.float32), _ptr(pos_new, torch.int32),
-        _stream(stream)), "kvtrim_paged_append")
+        int(n_new), _stream(stream)), "kvtrim_paged_append")
 
 
 def kvtrim_paged_score(ctx, cache, now, score_out, stream=None):

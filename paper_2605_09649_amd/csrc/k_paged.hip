@@ -165,6 +165,137 @@ __global__ __launch_bounds__(256) void k_pg_append(PagedView pc, const uint16_t*
     }
 }
 
+// Append of up to n_new tokens per segment (a prefill chunk): one block per segment.  The segment's
+// tokens - its rows up to the first negative position - first fill the empty slots of its pages, in
+// page order, and the rest goes to pages popped from the free stack in one step.  Whether the pages
+// are there is decided before anything is written, so a segment without room is left unchanged.
+constexpr int PGA_THREADS = 256;
+constexpr int PGA_MAX_NEW = 4096;          // tokens per segment and call (the slot of every token sits in LDS)
+
+__global__ __launch_bounds__(PGA_THREADS) void k_pg_append_n(PagedView pc, const uint16_t* __restrict__ k_new,
+                                                             const uint16_t* __restrict__ v_new,
+                                                             const float* __restrict__ lb_new,
+                                                             const float* __restrict__ lt_new,
+                                                             const int32_t* __restrict__ pos_new, int n_new, int head_dim,
+                                                             int32_t* err) {
+    __shared__ int32_t s_entry[PGA_MAX_NEW];                         // slot (flat entry index) of every token
+    __shared__ int32_t lds32[17];
+    __shared__ int s_cnt, s_first_new, s_ok;
+    const int tid = threadIdx.x, g = blockIdx.x;
+    if (tid == 0) s_cnt = n_new;
+    __syncthreads();
+    for (int i = tid; i < n_new; i += PGA_THREADS)
+        if (pos_new[(int64_t)g * n_new + i] < 0) atomicMin(&s_cnt, i);
+    __syncthreads();
+    const int cnt = s_cnt;                                           // tokens before the first padding row
+    if (cnt == 0) return;
+    const int npg = pc.seg_pages[g];
+    if (npg < 0 || npg > pc.max_pps) {
+        if (tid == 0) atomicOr(err, ERR_LAYOUT);
+        return;
+    }
+    int32_t* bt = pc.block_table + (int64_t)g * pc.max_pps;
+
+    // free slots of the segment's pages
+    int32_t free_total = 0;
+    for (int base = 0; base < npg; base += PGA_THREADS) {
+        const int i = base + tid;
+        int32_t f = 0;
+        if (i < npg) {
+            const int pg = bt[i];
+            if (pg >= 0 && pg < pc.n_pages) f = max(0, P - pc.page_live[pg]);
+        }
+        free_total += block_sum<int32_t>(f, lds32);
+    }
+    const int fill = min(cnt, (int)free_total);                      // tokens that go into holes
+    const int np = (cnt - fill + P - 1) / P;                         // new pages
+    if (tid == 0) {
+        s_ok = 1;
+        s_first_new = 0;
+        if (np > 0) {
+            if (npg + np > pc.max_pps) {
+                s_ok = 0;
+            } else {
+                const int idx = atomicSub(pc.n_free, np) - np;       // our pages: free_list[idx .. idx + np)
+                if (idx < 0) {
+                    atomicAdd(pc.n_free, np);
+                    s_ok = 0;
+                } else {
+                    s_first_new = idx;
+                }
+            }
+            if (!s_ok) atomicOr(err, ERR_CAP);
+        }
+    }
+    __syncthreads();
+    if (!s_ok) return;
+
+    // holes: page i takes the tokens [before_i, before_i + take_i), one thread per page walks its slots
+    int32_t before = 0;
+    for (int base = 0; base < npg && before < fill; base += PGA_THREADS) {
+        const int i = base + tid;
+        int pg = -1;
+        int32_t f = 0;
+        if (i < npg) {
+            pg = bt[i];
+            if (pg >= 0 && pg < pc.n_pages) f = max(0, P - pc.page_live[pg]);
+            else pg = -1;
+        }
+        int32_t tot;
+        const int32_t ex = before + block_excl_scan<int32_t>(f, lds32, &tot);
+        if (pg >= 0 && f > 0 && ex < fill) {
+            const int take = min((int)f, fill - (int)ex);
+            int done = 0;
+            for (int sl = 0; sl < P && done < take; ++sl) {
+                const int64_t e = (int64_t)pg * P + sl;
+                if (pc.pos[e] < 0) s_entry[ex + done++] = (int32_t)e;
+            }
+            if (done != take) atomicOr(err, ERR_LAYOUT);             // page_live disagrees with the slots
+            for (int d = done; d < take; ++d) s_entry[ex + d] = (int32_t)((int64_t)pg * P);   // stay in bounds
+            pc.page_live[pg] += take;
+        }
+        before += tot;
+    }
+    // new pages, popped from the top of the stack downwards
+    const int rest = cnt - fill;
+    for (int j = tid; j < np; j += PGA_THREADS) {
+        int pg = pc.free_list[s_first_new + np - 1 - j];
+        if (pg < 0 || pg >= pc.n_pages) {
+            atomicOr(err, ERR_LAYOUT);
+            pg = 0;
+        }
+        bt[npg + j] = pg;
+        pc.page_owner[pg] = g;
+        pc.page_live[pg] = min(P, rest - j * P);
+    }
+    __syncthreads();
+    for (int t = tid; t < rest; t += PGA_THREADS) s_entry[fill + t] = bt[npg + t / P] * P + t % P;
+    __syncthreads();
+
+    // rows and per-entry metadata
+    const int vpr = head_dim / 8;
+    const uint4* ks = reinterpret_cast<const uint4*>(k_new) + (int64_t)g * n_new * vpr;
+    const uint4* vs = reinterpret_cast<const uint4*>(v_new) + (int64_t)g * n_new * vpr;
+    uint4* kd = reinterpret_cast<uint4*>(pc.k);
+    uint4* vd = reinterpret_cast<uint4*>(pc.v);
+    for (int i = tid; i < cnt * vpr; i += PGA_THREADS) {
+        const int t = i / vpr, c = i - t * vpr;
+        const int64_t e = s_entry[t];
+        kd[e * vpr + c] = ks[i];
+        vd[e * vpr + c] = vs[i];
+    }
+    for (int t = tid; t < cnt; t += PGA_THREADS) {
+        const int64_t e = s_entry[t];
+        pc.log_beta[e] = lb_new[(int64_t)g * n_new + t];
+        if (pc.log_tail) pc.log_tail[e] = lt_new[(int64_t)g * n_new + t];
+        pc.pos[e] = pos_new[(int64_t)g * n_new + t];
+    }
+    if (tid == 0) {
+        pc.seg_pages[g] = npg + np;
+        pc.seg_live[g] += cnt;
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Score: a block takes PG_PER_BLOCK pages; a thread takes four consecutive slots (16-byte loads
 // and stores).  Empty slots of a segment's pages get 0; free pages are skipped.
@@ -726,18 +857,23 @@ kvtrim_status kvtrim_paged_build(kvtrim_ctx* ctx, const kvtrim_cache* src, const
 
 kvtrim_status kvtrim_paged_append(kvtrim_ctx* ctx, kvtrim_paged_cache* c, const void* k_new, const void* v_new,
                                   const float* log_beta_new, const float* log_tail_new, const int32_t* pos_new,
-                                  void* hip_stream) {
+                                  int32_t n_new, void* hip_stream) {
     if (!ctx) return KVTRIM_EINVAL;
     if (const char* p = paged_problem(ctx, c)) return bad(ctx, p);
     if (!k_new || !v_new || !log_beta_new || !pos_new) return bad(ctx, "a new-token pointer is NULL");
     if ((((uintptr_t)k_new) | ((uintptr_t)v_new)) & 15) return bad(ctx, "k_new / v_new not 16-byte aligned");
     if ((c->log_tail == nullptr) != (log_tail_new == nullptr))
         return bad(ctx, "log_tail_new is required exactly when the cache carries log_tail");
+    if (n_new < 1 || n_new > PGA_MAX_NEW) return bad(ctx, "n_new outside [1, 4096]");
     hipStream_t st = (hipStream_t)hip_stream;
     ProfScope prof(ctx, K_PG_APPEND, st);
-    hipLaunchKernelGGL(k_pg_append, dim3((ctx->shape.nseg + 3) / 4), dim3(256), 0, st, view_of(c), (const uint16_t*)k_new,
-                       (const uint16_t*)v_new, log_beta_new, log_tail_new, pos_new, ctx->shape.nseg, ctx->shape.head_dim,
-                       ctx->ws.err);
+    if (n_new == 1)
+        hipLaunchKernelGGL(k_pg_append, dim3((ctx->shape.nseg + 3) / 4), dim3(256), 0, st, view_of(c), (const uint16_t*)k_new,
+                           (const uint16_t*)v_new, log_beta_new, log_tail_new, pos_new, ctx->shape.nseg, ctx->shape.head_dim,
+                           ctx->ws.err);
+    else
+        hipLaunchKernelGGL(k_pg_append_n, dim3(ctx->shape.nseg), dim3(PGA_THREADS), 0, st, view_of(c), (const uint16_t*)k_new,
+                           (const uint16_t*)v_new, log_beta_new, log_tail_new, pos_new, n_new, ctx->shape.head_dim, ctx->ws.err);
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;
 }

@@ -227,3 +227,93 @@ def run_paged_both(w, budgets, device="cuda:0", cache_dict=None, now0=None, n_pa
         results.append(res)
         hc = hc_next
     return results
+
+
+def run_multiturn_paged(w, lengths, chunk, decode_per_turn, budget, device="cuda:0", turns=4):
+    """The chunked multi-turn flow on the paged layout: pages start empty; every turn appends each sequence's tokens
+    in chunks (ragged last chunks padded with negative positions), with score + select + evict after every chunk,
+    then decodes a few tokens with attention.  The oracle runs the same flow on its ragged cache."""
+    per_seq = w.n_layers * w.n_kv_heads
+    S, nseg, D = w.n_seq, w.nseg, w.head_dim
+    live_bound = sum(min(int(budget[s]), (lengths[s] + turns * decode_per_turn) * per_seq) for s in range(S))
+    n_pages = (live_bound + nseg * chunk) // P + 3 * nseg + 8
+    cap = live_bound + 2 * nseg * chunk + 8
+    shape = oracle.Shape(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim)
+    hc = oracle.HostCache(shape, cap)
+    hc.seg_start[:] = np.arange(nseg, dtype=np.int64) * chunk
+    ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, D, max(cap, n_pages * P))
+    pc = kv.PagedCache(nseg, D, n_pages, n_pages, device)
+    empty = kv.Cache.empty(nseg, D, 8, device)                     # pages are initialised from an empty ragged cache
+    kv.kvtrim_paged_build(ctx, empty, torch.zeros(8, dtype=torch.uint8, device=device),
+                          torch.zeros(nseg, dtype=torch.int32, device=device), pc)
+    slots = n_pages * P
+    score = torch.zeros(slots, dtype=torch.float32, device=device)
+    keep = torch.zeros(slots, dtype=torch.uint8, device=device)
+    kept = torch.zeros(nseg, dtype=torch.int32, device=device)
+    thr = torch.zeros(S, dtype=torch.int32, device=device)
+    budget_np = np.array(list(budget), np.int64)
+    budget_dev = torch.from_numpy(budget_np).to(device)
+    out = torch.zeros(S, w.n_layers, w.n_q_heads, D, dtype=torch.float32, device=device)
+    lse = torch.zeros(S, w.n_layers, w.n_q_heads, dtype=torch.float32, device=device)
+    scale = 1.0 / math.sqrt(D)
+    next_pos = np.zeros(S, np.int64)
+    results = []
+
+    def one(pos_new, n_new, inp, attend_q, label):
+        nonlocal hc
+        now = (next_pos - 1).astype(np.int32)
+        oracle.append(hc, bf16_bits(inp["k_new"]), bf16_bits(inp["v_new"]), inp["log_beta_new"].numpy(), pos_new)
+        s_ref = oracle.score(hc, now)
+        k_ref, kept_ref, thr_ref = oracle.select(hc, s_ref, budget_np)
+        live = live_mask(hc)
+        hc_next = oracle.compact(hc, k_ref, cap, chunk)
+        d = {k: v.to(device) for k, v in inp.items()}
+        kv.kvtrim_paged_append(ctx, pc, d["k_new"], d["v_new"], d["log_beta_new"], torch.from_numpy(pos_new).to(device),
+                               n_new=n_new)
+        kv.kvtrim_paged_score(ctx, pc, torch.from_numpy(now).to(device), score)
+        kv.kvtrim_paged_select(ctx, pc, score, budget_dev, keep, kept, thr)
+        res = {"what": label, "status_select": kv.kvtrim_poll_error(ctx)}
+        pre = PagedHost(pc, rows=False)
+        res["structure_pre"] = pre.structure_problems()
+        idx, counts = pre.ordered_slots()
+        same = np.array_equal(counts, hc.seg_len)
+        res["score_equal"] = bool(same and np.array_equal(score.cpu().numpy()[idx].view(np.uint32), s_ref[live].view(np.uint32)))
+        res["keep_equal"] = bool(same and np.array_equal(keep.cpu().numpy()[idx], k_ref[live]))
+        kv.kvtrim_paged_evict(ctx, pc, keep)
+        if attend_q is not None:
+            kv.kvtrim_paged_attn(ctx, pc, attend_q.to(device), 0, w.n_layers, scale, out, lse)
+        res["status"] = kv.kvtrim_poll_error(ctx)
+        res["kept_equal"] = bool(np.array_equal(kept.cpu().numpy(), kept_ref)
+                                 and np.array_equal(thr.cpu().numpy().view(np.uint32), thr_ref))
+        ph = PagedHost(pc)
+        res["structure"] = ph.structure_problems()
+        res["cache_equal"] = ph.equals(hc_next)
+        res["pages_in_use"] = int(ph.seg_pages.sum())
+        if attend_q is not None:
+            out_ref, lse_ref = oracle.attend(hc_next, bf16_bits(attend_q), scale)
+            res.update(attn_result(out.cpu().numpy(), lse.cpu().numpy(), out_ref, lse_ref))
+        results.append(res)
+        hc = hc_next
+
+    turn_len = [[(lengths[s] // turns) + (lengths[s] % turns if t == turns - 1 else 0) for t in range(turns)] for s in range(S)]
+    for t in range(turns):
+        left = np.array([turn_len[s][t] for s in range(S)], np.int64)
+        c = 0
+        while left.max() > 0:
+            take = np.minimum(left, chunk)
+            pos_new = np.full((nseg, chunk), -1, np.int32)
+            for s in range(S):
+                row = np.full(chunk, -1, np.int32)
+                row[:take[s]] = next_pos[s] + np.arange(take[s])
+                pos_new[s * per_seq:(s + 1) * per_seq] = row
+            next_pos += take
+            left -= take
+            one(pos_new, chunk, ki.chunk_inputs(w, chunk, "cpu", t, c), None, f"turn {t} chunk {c}")
+            c += 1
+        for dstep in range(decode_per_turn):
+            inp = ki.decode_inputs(w, t * 1000 + dstep)
+            pos_new = np.repeat(next_pos, per_seq).astype(np.int32).reshape(nseg, 1)
+            next_pos += 1
+            q = inp.pop("q")
+            one(pos_new, 1, inp, q, f"turn {t} decode {dstep}")
+    return results

@@ -200,3 +200,49 @@ def test_paged_append_skips_segments_whose_position_is_negative():
     assert list(ph.seg_pages) == [3, 2, 2, 1]                      # the full page of segment 2 made it take a new one
     idx, counts = ph.ordered_slots()
     assert ph.pos[idx[300 + 200 + 128]] == 9000 and ph.pos[idx[-1]] == 9000
+
+
+def check_flow(results):
+    for r in results:
+        assert r["status"] == 0 and r["status_select"] == 0, r
+        assert r["structure"] == [] and r["structure_pre"] == [], r
+        assert r["score_equal"] and r["keep_equal"] and r["kept_equal"] and r["cache_equal"], r
+        if "attn_err" in r:
+            assert r["attn_err"] <= ATTN_TOL and r["lse_err"] <= 2e-3 and r["lse_inf_equal"], r
+
+
+def test_multi_turn_chunked_prefill_into_pages():
+    # pages start empty; chunks of 200 tokens (more than a page) fill holes first, then take new pages; sequences of
+    # different lengths (ragged last chunks), per-sequence budgets, four turns with decode steps in between
+    from paged_harness import run_multiturn_paged
+    w = wl(3, 2, 2, 2, 64)
+    res = run_multiturn_paged(w, [1500, 380, 811], chunk=200, decode_per_turn=3, budget=[300, 10 ** 6, 170], device=DEV)
+    assert len(res) >= 20
+    check_flow(res)
+    pages = [r["pages_in_use"] for r in res]
+    assert max(pages) > pages[-1] or max(pages) > min(pages[5:])     # pages were given back along the way
+
+
+def test_multi_turn_chunked_sixteen_sequences_into_pages():
+    from paged_harness import run_multiturn_paged
+    w = ki.workload("multiturn", prefill=1024)                   # S16 L32 Hkv8 Hq32 D128, lengths in [64, 1024]
+    check_flow(run_multiturn_paged(w, list(w.prefill), chunk=256, decode_per_turn=2, budget=[96 * 32 * 8] * 16, device=DEV,
+                                   turns=2))
+
+
+def test_chunk_append_without_pages_leaves_the_segment_unchanged():
+    w, ctx, src, pc, keep, kept = _small_setup(n_pages=5, max_pps=8, seg_len=(250, 100))
+    kv.kvtrim_paged_build(ctx, src, keep, kept, pc)
+    assert kv.kvtrim_poll_error(ctx) == 0
+    before = PagedHost(pc)
+    assert before.n_free == 2
+    inp = {k: v.to(DEV) for k, v in ki.chunk_inputs(w, 300, "cpu", 1).items()}
+    pos = torch.arange(5000, 5300, dtype=torch.int32).repeat(w.nseg, 1)
+    pos[1, 40:] = -1                                             # segment 1 brings 40 tokens, segment 0 all 300
+    kv.kvtrim_paged_append(ctx, pc, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos.to(DEV), n_new=300)
+    assert kv.kvtrim_poll_error(ctx) == -4                       # segment 0 needs 3 more pages, 2 are free
+    after = PagedHost(pc)
+    assert after.structure_problems() == []
+    assert list(after.seg_live) == [250, 140] and after.n_free == 1   # segment 1 filled its hole and took one page
+    with pytest.raises(kv.KvtrimError):
+        kv.kvtrim_paged_append(ctx, pc, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos.to(DEV), n_new=5000)
