@@ -324,7 +324,7 @@ kvtrim_status kvtrim_gate_forward(kvtrim_ctx *ctx, const kvtrim_gate *g, const v
  * end waits for `hip_stream` and writes, per kernel id, the summed duration in
  * milliseconds and the number of bracketed launches into host arrays of
  * KVTRIM_N_KERNELS elements.  Do not capture a HIP graph while profiling is on. */
-#define KVTRIM_N_KERNELS 25
+#define KVTRIM_N_KERNELS 27
 #define KVTRIM_PROFILE_MAX_LAUNCHES 4096
 kvtrim_status kvtrim_profile_begin(kvtrim_ctx *ctx, uint32_t kernel_mask);
 kvtrim_status kvtrim_profile_end(kvtrim_ctx *ctx, void *hip_stream, double *ms_sum_host,

@@ -322,9 +322,274 @@ __global__ __launch_bounds__(GR_THREADS) void k_gate_readout(GateView g, const f
     }
 }
 
+// ---- Many tokens per call (a prefill chunk): the second layer and the tied readout are both linear, so
+//     z = w_g . (W2 u + c2) + b_g = v . u + s,   v = W2^T w_g  (d_g numbers per (layer, head)),  s = w_g . c2 + b_g
+// k_gate_fold computes v and s for the call's weights (one pass over W2), and k_gate_prefill then needs no
+// second contraction: a block owns 128 tokens and ALL d_g hidden units of one layer, keeps u in its MFMA
+// accumulators, and finishes with eight dot products per token on the vector ALU - u never goes to memory
+// and every token row is read once.
+//
+// Fold: one block per (layer, head).  A wavefront reads whole rows of W2 (a lane owns 8 columns, 16 bytes, of
+// every 512-column stretch), the eight wavefronts take every eighth row, and their partial vectors meet in LDS.
+constexpr int GF_THREADS = 512, GF_COLS = 512;
+
+__global__ __launch_bounds__(GF_THREADS) void k_gate_fold(GateView g, int layer_begin, int n_heads, float* __restrict__ v,
+                                                          float* __restrict__ s) {
+    __shared__ __align__(16) float s_part[GF_THREADS / 64][GF_COLS];
+    __shared__ float s_red[GF_THREADS / 64];
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    const int head = blockIdx.x, lr = blockIdx.y, layer = layer_begin + lr;
+    const uint16_t* w2 = g.w2 + ((size_t)layer * n_heads + head) * g.d_p * g.d_g;
+    const float* c2 = g.c2 + ((size_t)layer * n_heads + head) * g.d_p;
+    float* vout = v + ((size_t)lr * n_heads + head) * g.d_g;
+    for (int c0 = 0; c0 < g.d_g; c0 += GF_COLS) {                    // d_g is a multiple of 64: a lane's 8 columns are all in or all out
+        const int col = c0 + 8 * lane;
+        float a[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) a[e] = 0.f;
+        if (col < g.d_g) {
+#pragma unroll 4
+            for (int j = wave; j < g.d_p; j += GF_THREADS / 64) {
+                const uint4 w = *reinterpret_cast<const uint4*>(w2 + (size_t)j * g.d_g + col);
+                const float wg = g.w_g[j];
+                const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    a[2 * e] = fmaf(wg, __uint_as_float(ww[e] << 16), a[2 * e]);
+                    a[2 * e + 1] = fmaf(wg, __uint_as_float(ww[e] & 0xFFFF0000u), a[2 * e + 1]);
+                }
+            }
+        }
+        __syncthreads();                                             // the previous stretch has been summed
+        *reinterpret_cast<float4*>(&s_part[wave][8 * lane]) = make_float4(a[0], a[1], a[2], a[3]);
+        *reinterpret_cast<float4*>(&s_part[wave][8 * lane + 4]) = make_float4(a[4], a[5], a[6], a[7]);
+        __syncthreads();
+        if (tid < GF_COLS && c0 + tid < g.d_g) {
+            float t = 0.f;
+#pragma unroll
+            for (int w = 0; w < GF_THREADS / 64; ++w) t += s_part[w][tid];
+            vout[c0 + tid] = t;
+        }
+    }
+    float part = 0.f;
+    for (int j = tid; j < g.d_p; j += GF_THREADS) part = fmaf(g.w_g[j], c2[j], part);
+    part = wave_sum(part);
+    if (lane == 0) s_red[wave] = part;
+    __syncthreads();
+    if (tid == 0) {
+        float t = g.b_g;
+#pragma unroll
+        for (int w = 0; w < GF_THREADS / 64; ++w) t += s_red[w];
+        s[(size_t)lr * n_heads + head] = t;
+    }
+}
+
+// Prefill: 512 threads = 8 wavefronts.  Wavefront w owns hidden units [w*16*HT, (w+1)*16*HT) (d_g = 128*HT)
+// for all 16*TT tokens of the block: HT x TT accumulator tiles of 16 x 16 (TT = 8 for long calls; 4 or 2 when
+// 128-token blocks would be too few to fill the chip).  Its rows of W1 come straight from global memory
+// in MFMA operand layout (a lane loads 32 contiguous bytes of its row per 64-wide step and feeds the halves
+// to two MFMAs; four lanes cover one 128-byte line), one step ahead in registers.  The token rows are shared
+// by all wavefronts: wavefront j < TT loads token tile j the same way and parks it in LDS, one KB per operand
+// fragment in lane order (reads and writes are contiguous, no bank conflicts), double buffered, one barrier
+// per step.  Block ids are mapped so that the blocks an XCD runs at one time belong to one layer (ids are
+// dealt to the eight XCDs in turn), so W1_l is shared through that XCD's L2.
+constexpr int GP_THREADS = 512, GP_HEADS_MAX = 8;
+
+template <int HT, int TT>
+__global__ __launch_bounds__(GP_THREADS) void k_gate_prefill(GateView g, const uint16_t* __restrict__ x, int n_tok,
+                                                             int layer_begin, int nl, int n_layers, int n_heads, int horizon,
+                                                             const float* __restrict__ v, const float* __restrict__ sconst,
+                                                             float* __restrict__ log_beta_out,
+                                                             float* __restrict__ log_tail_out) {
+    constexpr int GP_TOK = 16 * TT;
+    // [buffer][token tile][half of the step][lane], 4 TT KB; after the loop [wave][head][token] floats, also 4 TT KB
+    __shared__ __align__(16) uint4 s_x[2][TT][2][64];
+    const int tid = threadIdx.x, lane = lane_id();
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);       // uniform: addresses below stay scalar base + lane offset
+    const int r16 = lane & 15, g4 = lane >> 4;
+    const int tiles = (n_tok + GP_TOK - 1) / GP_TOK;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int lr = (slot / tiles) * 8 + xcd;
+    if (lr >= nl) return;                                            // whole block, before any barrier
+    const int tok0 = (slot % tiles) * GP_TOK;
+    const int layer = layer_begin + lr;
+    const int hid0 = wave * 16 * HT;
+
+    // byte addresses: uniform base + 32-bit lane offset (16 rows of <= 2^20 bytes each)
+    const char* wbase = reinterpret_cast<const char*>(g.w1 + ((size_t)layer * g.d_g + hid0) * g.d_model);
+    const uint32_t row_bytes = 2u * (uint32_t)g.d_model;
+    const uint32_t aoff = (uint32_t)r16 * row_bytes + 32u * (uint32_t)g4;
+    const int tile_tok0 = tok0 + 16 * min(wave, TT - 1);             // rows past the end repeat the last token, never written
+    const char* xbase = reinterpret_cast<const char*>(x + ((size_t)lr * n_tok + min(tile_tok0, n_tok - 1)) * g.d_model);
+    const uint32_t xoff = (uint32_t)min(r16, max(n_tok - 1 - tile_tok0, 0)) * row_bytes + 32u * (uint32_t)g4;
+
+    gate_f4 acc[HT][TT];
+#pragma unroll
+    for (int i = 0; i < HT; ++i)
+#pragma unroll
+        for (int j = 0; j < TT; ++j) acc[i][j] = gate_f4{0.f, 0.f, 0.f, 0.f};
+
+    const int steps = g.d_model >> 6;                                // 64 contraction indices = 128 bytes of a row per step
+    auto col = [&](int kt) { return (size_t)kt * 128; };
+    uint4 a0[HT][2], a1[HT][2], xr0, xr1;
+    auto load_a = [&](int kt, uint4 (&a)[HT][2]) {
+#pragma unroll
+        for (int i = 0; i < HT; ++i) {
+            const uint4* p = reinterpret_cast<const uint4*>(wbase + (size_t)i * 16 * row_bytes + col(kt) + aoff);
+            a[i][0] = p[0];
+            a[i][1] = p[1];
+        }
+    };
+    // uniform per wavefront; a compile-time "true" in the full-size variant keeps its loop free of branches
+    const bool loader = TT == 8 || wave < TT;
+    xr0 = xr1 = make_uint4(0, 0, 0, 0);
+    auto load_x = [&](int kt) {
+        if (TT == 8 || loader) {
+            const uint4* p = reinterpret_cast<const uint4*>(xbase + col(kt) + xoff);
+            xr0 = p[0];
+            xr1 = p[1];
+        }
+    };
+    auto park_x = [&](int buf) {
+        if (TT == 8 || loader) {
+            s_x[buf][wave][0][lane] = xr0;
+            s_x[buf][wave][1][lane] = xr1;
+        }
+    };
+    auto multiply = [&](int buf, const uint4 (&a)[HT][2]) {
+        uint4 b = s_x[buf][0][0][lane];
+#pragma unroll
+        for (int f = 0; f < 2 * TT; ++f) {                           // fragment f = (half f / TT, token tile f % TT); one read ahead
+            uint4 bn = b;
+            if (f + 1 < 2 * TT) bn = s_x[buf][(f + 1) % TT][(f + 1) / TT][lane];
+#pragma unroll
+            for (int i = 0; i < HT; ++i) acc[i][f % TT] = mma_bf16(a[i][f / TT], b, acc[i][f % TT]);
+            b = bn;
+            __builtin_amdgcn_sched_barrier(0);                       // keeps the compiler from hoisting all the reads (spills)
+        }
+    };
+    load_x(0);
+    load_a(0, a0);
+    park_x(0);
+    __syncthreads();
+    load_x(1);                                                       // x before W1: parking x then waits for its own load only
+    load_a(1, a1);
+    // Two steps per trip (steps is a multiple of 4).  The loop body has no branches: past the end the loads
+    // repeat the last step and park it in a buffer nobody reads any more.
+    const int last = steps - 1;
+    for (int kt = 0; kt < steps; kt += 2) {
+        multiply(0, a0);
+        park_x(1);                                                   // step kt+1; buffer 1 was last read before the previous barrier
+        __syncthreads();
+        load_x(min(kt + 2, last));
+        load_a(min(kt + 2, last), a0);
+        multiply(1, a1);
+        park_x(0);
+        __syncthreads();
+        load_x(min(kt + 3, last));
+        load_a(min(kt + 3, last), a1);
+    }
+
+    // acc[i][j][r] = pre-activation of (hidden hid0 + 16 i + 4 g4 + r, token tok0 + 16 j + r16)
+#pragma unroll
+    for (int i = 0; i < HT; ++i) {
+        const float4 c = *reinterpret_cast<const float4*>(g.c1 + (size_t)layer * g.d_g + hid0 + 16 * i + 4 * g4);
+        const float cc[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+        for (int j = 0; j < TT; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float t = acc[i][j][r] + cc[r];
+                acc[i][j][r] = t / (1.0f + __expf(-t));
+            }
+    }
+    float* s_z = reinterpret_cast<float*>(&s_x[0][0][0][0]);         // every wavefront is past the last barrier of the loop
+    for (int h = 0; h < n_heads; ++h) {
+        const float* vh = v + ((size_t)lr * n_heads + h) * g.d_g + hid0 + 4 * g4;
+        float zp[TT];
+#pragma unroll
+        for (int j = 0; j < TT; ++j) zp[j] = 0.f;
+#pragma unroll
+        for (int i = 0; i < HT; ++i) {
+            const float4 w = *reinterpret_cast<const float4*>(vh + 16 * i);
+            const float ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+            for (int j = 0; j < TT; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) zp[j] = fmaf(ww[r], acc[i][j][r], zp[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < TT; ++j) {
+            float t = zp[j];
+            t += __shfl_xor(t, 16, 64);
+            t += __shfl_xor(t, 32, 64);
+            if (g4 == 0) s_z[(wave * GP_HEADS_MAX + h) * GP_TOK + 16 * j + r16] = t;
+        }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < n_heads * GP_TOK; idx += GP_THREADS) {
+        const int h = idx / GP_TOK, tk = idx - h * GP_TOK;
+        const int tok = tok0 + tk;
+        if (tok >= n_tok) continue;
+        float z = sconst[(size_t)lr * n_heads + h];
+#pragma unroll
+        for (int w = 0; w < 8; ++w) z += s_z[(w * GP_HEADS_MAX + h) * GP_TOK + tk];
+        const float lb = log_sigmoid(z);
+        const size_t o = ((size_t)tok * n_layers + layer) * n_heads + h;
+        log_beta_out[o] = lb;
+        if (log_tail_out) log_tail_out[o] = log_tail_of(lb, horizon);
+    }
+}
+
+// Below this many tokens the fold's extra pass over W2 and the few blocks of the prefill kernel do not pay.
+#ifndef KVTRIM_GATE_PREFILL_MIN_TOK
+#define KVTRIM_GATE_PREFILL_MIN_TOK 256
+#endif
+constexpr int GP_MIN_TOK = KVTRIM_GATE_PREFILL_MIN_TOK;
+
+static bool prefill_shape(const kvtrim_ctx* ctx, const GateView& g) {
+    return g.d_g % 128 == 0 && g.d_g <= 512 && ctx->shape.n_kv_heads <= GP_HEADS_MAX;
+}
+
 kvtrim_status launch_gate(kvtrim_ctx* ctx, const GateView& g, const uint16_t* x, int n_tok, int layer_begin, int layer_end,
                           int horizon, float* scratch, float* log_beta_out, float* log_tail_out, hipStream_t st) {
     const int nl = layer_end - layer_begin;
+    const int n_heads = ctx->shape.n_kv_heads;
+    if (n_tok >= GP_MIN_TOK && prefill_shape(ctx, g)) {
+        float* v = scratch;                                          // [nl][heads][d_g]
+        float* sconst = scratch + (size_t)nl * n_heads * g.d_g;      // [nl][heads]
+        {
+            ProfScope prof(ctx, K_GATE_FOLD, st);
+            hipLaunchKernelGGL(k_gate_fold, dim3(n_heads, nl), dim3(GF_THREADS), 0, st, g, layer_begin, n_heads, v, sconst);
+        }
+        {
+            ProfScope prof(ctx, K_GATE_PREFILL, st);
+            // tokens per block: 128, or 64 / 32 while that is what it takes to have a block for every compute unit
+            int tt = 8;
+            while (tt > 2 && (int64_t)nl * ((n_tok + 16 * tt - 1) / (16 * tt)) < 256) tt >>= 1;
+            const int tiles = (n_tok + 16 * tt - 1) / (16 * tt);
+            const dim3 grid(8u * (unsigned)((nl + 7) / 8) * (unsigned)tiles);
+#define KVTRIM_GATE_PREFILL(HT, TT)                                                                                           \
+    hipLaunchKernelGGL((k_gate_prefill<HT, TT>), grid, dim3(GP_THREADS), 0, st, g, x, n_tok, layer_begin, nl,                 \
+                       ctx->shape.n_layers, n_heads, horizon, v, sconst, log_beta_out, log_tail_out)
+#define KVTRIM_GATE_PREFILL_TT(HT)                                                                                            \
+    do {                                                                                                                      \
+        if (tt == 8) KVTRIM_GATE_PREFILL(HT, 8);                                                                              \
+        else if (tt == 4) KVTRIM_GATE_PREFILL(HT, 4);                                                                         \
+        else KVTRIM_GATE_PREFILL(HT, 2);                                                                                      \
+    } while (0)
+            switch (g.d_g / 128) {
+                case 1: KVTRIM_GATE_PREFILL_TT(1); break;
+                case 2: KVTRIM_GATE_PREFILL_TT(2); break;
+                case 3: KVTRIM_GATE_PREFILL_TT(3); break;
+                default: KVTRIM_GATE_PREFILL_TT(4); break;
+            }
+#undef KVTRIM_GATE_PREFILL_TT
+#undef KVTRIM_GATE_PREFILL
+        }
+        KVTRIM_HIP(ctx, hipGetLastError());
+        return KVTRIM_OK;
+    }
     {
         ProfScope prof(ctx, K_GATE_HIDDEN, st);
         const dim3 grid1(g.d_g / GH_ROWS, nl, 1);
@@ -341,8 +606,8 @@ kvtrim_status launch_gate(kvtrim_ctx* ctx, const GateView& g, const uint16_t* x,
     }
     {
         ProfScope prof(ctx, K_GATE_READOUT, st);
-        hipLaunchKernelGGL(k_gate_readout, dim3(ctx->shape.n_kv_heads, nl, (n_tok + 15) / 16), dim3(GR_THREADS), 0, st, g, scratch,
-                           n_tok, layer_begin, ctx->shape.n_layers, ctx->shape.n_kv_heads, horizon, log_beta_out, log_tail_out);
+        hipLaunchKernelGGL(k_gate_readout, dim3(n_heads, nl, (n_tok + 15) / 16), dim3(GR_THREADS), 0, st, g, scratch,
+                           n_tok, layer_begin, ctx->shape.n_layers, n_heads, horizon, log_beta_out, log_tail_out);
     }
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;
@@ -356,6 +621,8 @@ extern "C" {
 
 size_t kvtrim_gate_scratch_bytes(const kvtrim_gate* g, int32_t n_tok, int32_t n_layers) {
     if (!g || n_tok < 1 || n_layers < 1 || g->d_g < 1) return 0;
+    // u for the per-token kernels; the prefill kernels keep (heads <= 8) * (d_g + 1) numbers per layer there and
+    // run only from GP_MIN_TOK tokens on, so they always fit
     return (size_t)n_tok * (size_t)n_layers * (size_t)g->d_g * sizeof(float);
 }
 

@@ -22,12 +22,15 @@ DEV = "cuda:0"
 RTOL = 2e-4
 
 
-def run_both(L, H, d_model, d_g, d_p, n_tok, b_g=3.5, layer_begin=0, layer_end=None, horizon=None, salt=0):
+def run_both(L, H, d_model, d_g, d_p, n_tok, b_g=3.5, layer_begin=0, layer_end=None, horizon=None, salt=0, pick=None):
+    """GPU on all n_tok tokens; the oracle on all of them, or on the tokens listed in `pick` (a token's
+    gates do not depend on the other tokens of the call) - the GPU rows are then cut to the same list."""
     layer_end = L if layer_end is None else layer_end
     w = ki.gate_weights(L, H, d_model, d_g, d_p, b_g=b_g, seed=1234 + salt)
     x = ki.gate_inputs(L, n_tok, d_model, salt=salt)[layer_begin:layer_end].contiguous()
     og = oracle.Gate(bf16_bits(w["w1"]), w["c1"].numpy(), bf16_bits(w["w2"]), w["c2"].numpy(), w["w_g"].numpy(), b_g)
-    z_ref, lb_ref, lt_ref = oracle.gate_forward(og, bf16_bits(x), layer_begin, layer_end, horizon)
+    x_ref = x if pick is None else x[:, pick].contiguous()
+    z_ref, lb_ref, lt_ref = oracle.gate_forward(og, bf16_bits(x_ref), layer_begin, layer_end, horizon)
     ctx = kv.Context(1, L, H, H, 64, 1024)
     gate = kv.Gate.from_dict(w, DEV)
     nl = layer_end - layer_begin
@@ -37,6 +40,9 @@ def run_both(L, H, d_model, d_g, d_p, n_tok, b_g=3.5, layer_begin=0, layer_end=N
     kv.kvtrim_gate_forward(ctx, gate, x.to(DEV), n_tok, layer_begin, layer_end, 0 if horizon is None else horizon,
                            scratch, lb, lt)
     assert kv.kvtrim_poll_error(ctx) == 0
+    if pick is not None:
+        lb = lb[pick]
+        lt = None if lt is None else lt[pick]
     return z_ref, lb_ref, lt_ref, lb.cpu().numpy(), None if lt is None else lt.cpu().numpy()
 
 
@@ -51,9 +57,14 @@ def rel_err(got, ref):
     (2, 2, 256, 576, 40, 17),         # hidden width beyond one staged chunk, token tail of one
     (1, 2, 512, 64, 33, 20),          # two token tiles per block
     (1, 2, 512, 64, 33, 64),          # four token tiles in one block
-    (1, 2, 512, 64, 33, 150),         # LDS-tiled first layer: hidden width below the 128-row tile, ragged token tail
-    (2, 2, 256, 192, 16, 300),        # ... 1.5 row tiles, 2.3 token tiles
-    (1, 1, 1024, 512, 128, 257),      # ... the paper's hidden width, one token beyond two tiles
+    (1, 2, 512, 64, 33, 150),         # four token tiles per block, three blocks along the tokens, ragged tail
+    (2, 2, 256, 192, 16, 300),        # LDS-tiled first layer (hidden width not a multiple of 128): 1.5 row tiles, 2.3 token tiles
+    (1, 2, 256, 576, 8, 256),         # ... hidden width above 512
+    (1, 1, 1024, 512, 128, 257),      # folded prefill path: the paper's hidden width, one token beyond two 128-token tiles
+    (2, 3, 512, 128, 20, 300),        # ... one 16-row tile per wavefront, three heads
+    (9, 2, 256, 256, 16, 260),        # ... nine layers: the second round of the layer-to-XCD dealing is partly empty
+    (1, 8, 256, 384, 5, 513),         # ... eight heads, three tiles per wavefront, token tail of one
+    (3, 2, 256, 512, 1, 256),         # ... exactly two full token tiles, scalar projection
 ])
 def test_gate_forward_matches_the_oracle(L, H, d_model, d_g, d_p, n_tok):
     z_ref, lb_ref, _, lb, _ = run_both(L, H, d_model, d_g, d_p, n_tok, salt=d_p)
@@ -79,6 +90,36 @@ def test_horizon_tail_constant(horizon):
         assert np.array_equal(lt, np.zeros_like(lt))
 
 
+def test_prefill_sized_call_with_a_layer_range_and_a_horizon():
+    # the folded path (256 tokens and more): layers outside the range stay untouched, the tail constant follows log beta
+    _, lb_ref, lt_ref, lb, lt = run_both(5, 2, 256, 128, 12, 300, b_g=1.0, layer_begin=1, layer_end=4, horizon=2)
+    assert np.isnan(lb[:, 0, :]).all() and np.isnan(lb[:, 4, :]).all()
+    assert np.isnan(lt[:, 0, :]).all() and np.isnan(lt[:, 4, :]).all()
+    assert rel_err(lb[:, 1:4, :], lb_ref[:, 1:4, :]) <= RTOL
+    assert np.max(np.abs(lt[:, 1:4, :] - lt_ref[:, 1:4, :])) <= 1e-3 * np.max(np.abs(lt_ref[:, 1:4, :])) + 1e-6
+
+
+def test_both_paths_agree_across_the_token_threshold():
+    # 255 tokens run the per-token kernels, 256 the folded ones: the shared 255 tokens get the same gates to rounding
+    L, H, d_model, d_g, d_p = 2, 2, 512, 256, 24
+    w = ki.gate_weights(L, H, d_model, d_g, d_p, b_g=3.5, seed=77)
+    x = ki.gate_inputs(L, 256, d_model, salt=3)
+    og = oracle.Gate(bf16_bits(w["w1"]), w["c1"].numpy(), bf16_bits(w["w2"]), w["c2"].numpy(), w["w_g"].numpy(), 3.5)
+    _, lb_ref, _ = oracle.gate_forward(og, bf16_bits(x), 0, L, None)
+    ctx = kv.Context(1, L, H, H, 64, 1024)
+    gate = kv.Gate.from_dict(w, DEV)
+    got = {}
+    for n_tok in (255, 256):
+        xd = x[:, :n_tok].contiguous().to(DEV)
+        scratch = torch.empty(kv.kvtrim_gate_scratch_bytes(gate, n_tok, L) // 4, dtype=torch.float32, device=DEV)
+        lb = torch.full((n_tok, L, H), float("nan"), dtype=torch.float32, device=DEV)
+        kv.kvtrim_gate_forward(ctx, gate, xd, n_tok, 0, L, 1, scratch, lb, None)
+        assert kv.kvtrim_poll_error(ctx) == 0
+        got[n_tok] = lb.cpu().numpy()
+        assert rel_err(got[n_tok], lb_ref[:n_tok]) <= RTOL
+    assert np.max(np.abs(got[255] - got[256][:255]) / np.abs(lb_ref[:255])) <= RTOL
+
+
 def test_initial_bias_of_eighteen_keeps_beta_next_to_one():
     # Sec. 5.1: b_g starts at 18.0 - log beta is about -1.5e-8 and must not flush to 0 or lose its digits
     z_ref, lb_ref, _, lb, _ = run_both(2, 2, 256, 64, 16, 4, b_g=18.0)
@@ -92,6 +133,15 @@ def test_full_size_gate_one_token_and_sixteen():
         err = rel_err(lb, lb_ref)
         print(f"n_tok {n_tok}: max relative error of log beta {err:.2e}")
         assert err <= RTOL
+
+
+def test_full_size_gate_prefill_chunk_on_sampled_tokens():
+    # a 2048-token chunk through the benchmark model; the oracle takes 12 of its tokens (tile edges and interiors)
+    pick = [0, 1, 15, 16, 127, 128, 1000, 1023, 1024, 1500, 2046, 2047]
+    z_ref, lb_ref, _, lb, _ = run_both(32, 8, 4096, 512, 128, 2048, salt=7, pick=pick)
+    err = rel_err(lb, lb_ref)
+    print(f"2048 tokens, {len(pick)} sampled: max relative error of log beta {err:.2e}")
+    assert err <= RTOL
 
 
 def test_host_side_argument_checks_of_the_gate():
