@@ -297,8 +297,10 @@ typedef struct {
     float b_g;
 } kvtrim_gate;
 
-/* Bytes of scratch kvtrim_gate_forward needs for n_tok tokens and n_layers layers of a range
- * (the hidden activations u in fp32); 0 for invalid arguments.  Host-only, no GPU call. */
+/* Bytes of scratch kvtrim_gate_forward needs for n_tok tokens and n_layers layers of a range:
+ * n_tok * n_layers * d_g floats (short calls keep the hidden activations u there in fp32; calls of 128 tokens
+ * and more keep the folded readout vectors there and, where it fits - from about d_model / 2 tokens on - a
+ * copy of W1 in matrix-core operand order); 0 for invalid arguments.  Host-only, no GPU call. */
 size_t kvtrim_gate_scratch_bytes(const kvtrim_gate *g, int32_t n_tok, int32_t n_layers);
 
 /* x: bf16 [layer_end - layer_begin][n_tok][d_model], 16-byte aligned, the representation of each
@@ -308,9 +310,11 @@ size_t kvtrim_gate_scratch_bytes(const kvtrim_gate *g, int32_t n_tok, int32_t n_
  *                              (Eq. global_score; NULL to skip; horizon in [0, 4096])
  * - with one token per sequence this is segment order, the layout kvtrim_append takes.
  * scratch: device memory, 16-byte aligned, at least kvtrim_gate_scratch_bytes(...) bytes, contents
- * undefined afterwards.  Enqueues two kernels on the stream; allocates nothing.  Arithmetic: bf16
- * products accumulated in fp32 on the matrix cores, u kept to 16 mantissa bits for the second
- * layer; results agree with an fp64 evaluation to about 1e-5 relative in log beta. */
+ * undefined afterwards.  Enqueues two or three kernels on the stream; allocates nothing.  Arithmetic:
+ * bf16 products accumulated in fp32 on the matrix cores.  Calls below 128 tokens carry u to 16 mantissa
+ * bits into the second layer; longer calls use that the second layer and the readout are both linear
+ * (z = (W2^T w_g) . u + w_g . c2 + b_g), fold them into one fp32 vector per (layer, head) first and keep u
+ * in fp32.  Results agree with an fp64 evaluation to about 1e-5 relative in log beta either way. */
 kvtrim_status kvtrim_gate_forward(kvtrim_ctx *ctx, const kvtrim_gate *g, const void *x, int32_t n_tok,
                                   int32_t layer_begin, int32_t layer_end, int32_t horizon, void *scratch,
                                   float *log_beta_out, float *log_tail_out, void *hip_stream);
@@ -324,7 +328,7 @@ kvtrim_status kvtrim_gate_forward(kvtrim_ctx *ctx, const kvtrim_gate *g, const v
  * end waits for `hip_stream` and writes, per kernel id, the summed duration in
  * milliseconds and the number of bracketed launches into host arrays of
  * KVTRIM_N_KERNELS elements.  Do not capture a HIP graph while profiling is on. */
-#define KVTRIM_N_KERNELS 27
+#define KVTRIM_N_KERNELS 28
 #define KVTRIM_PROFILE_MAX_LAUNCHES 4096
 kvtrim_status kvtrim_profile_begin(kvtrim_ctx *ctx, uint32_t kernel_mask);
 kvtrim_status kvtrim_profile_end(kvtrim_ctx *ctx, void *hip_stream, double *ms_sum_host,

@@ -19,7 +19,7 @@ EXPORTS = ["kvtrim_create", "kvtrim_destroy", "kvtrim_workspace_bytes", "kvtrim_
            "kvtrim_profile_begin", "kvtrim_profile_end",
            "kvtrim_kernel_name"]
 PAGE_SIZE = 128
-N_KERNELS = 27
+N_KERNELS = 28
 
 
 class KvtrimError(RuntimeError):

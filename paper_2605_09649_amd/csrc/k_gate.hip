@@ -384,26 +384,69 @@ __global__ __launch_bounds__(GF_THREADS) void k_gate_fold(GateView g, int layer_
     }
 }
 
+// Operand layout and the memory system.  A wavefront load that fetches an MFMA operand straight from a
+// row-major matrix touches 16 different rows in every group of 16 lanes; the vector L1 then serves about
+// 15 bytes per clock and compute unit (measured), against 50 for loads whose 16-lane groups read 256
+// contiguous bytes.  Hence:
+//   k_gate_retile  copies W1 once per call into tiles of 16 rows x 64 columns (2 KB) stored in lane order - the
+//                  two 16-byte halves a lane feeds to the two MFMAs of a step at [half][lane] - when the call
+//                  is long enough to pay for the pass and the scratch buffer has room;
+//   token rows     are loaded coalesced (8 lanes cover the 128 bytes of a row and step) and scattered into
+//                  operand order inside LDS, which they pass through anyway.
+// The contraction index of a step is permuted (both operands alike): lane group g of half h holds columns
+// 16 g + 8 h .. + 8.
+//
+// Retile: one wavefront per (layer, 16-row tile, 4 steps); reads in operand layout, writes 1 KB contiguous.
+constexpr int GT_THREADS = 256;
+
+__global__ __launch_bounds__(GT_THREADS) void k_gate_retile(GateView g, int layer_begin, uint4* __restrict__ tiled) {
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int r16 = lane & 15, g4 = lane >> 4;
+    const int steps = g.d_model >> 6;
+    const int tile = blockIdx.y, lr = blockIdx.z;
+    const int s0 = (blockIdx.x * (GT_THREADS / 64) + wave) * 4;      // steps is a multiple of 4
+    if (s0 >= steps) return;
+    const uint4* src = reinterpret_cast<const uint4*>(g.w1 + ((size_t)(layer_begin + lr) * g.d_g + 16 * tile + r16) * g.d_model +
+                                                      64 * s0 + 16 * g4);
+    uint4* dst = tiled + (((size_t)lr * (g.d_g >> 4) + tile) * steps + s0) * 128 + lane;
+    uint4 v[4][2];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        v[u][0] = src[8 * u];
+        v[u][1] = src[8 * u + 1];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        dst[128 * u] = v[u][0];
+        dst[128 * u + 64] = v[u][1];
+    }
+}
+
 // Prefill: 512 threads = 8 wavefronts.  Wavefront w owns hidden units [w*16*HT, (w+1)*16*HT) (d_g = 128*HT)
 // for all 16*TT tokens of the block: HT x TT accumulator tiles of 16 x 16 (TT = 8 for long calls; 4 or 2 when
-// 128-token blocks would be too few to fill the chip).  Its rows of W1 come straight from global memory
-// in MFMA operand layout (a lane loads 32 contiguous bytes of its row per 64-wide step and feeds the halves
-// to two MFMAs; four lanes cover one 128-byte line), one step ahead in registers.  The token rows are shared
-// by all wavefronts: wavefront j < TT loads token tile j the same way and parks it in LDS, one KB per operand
-// fragment in lane order (reads and writes are contiguous, no bank conflicts), double buffered, one barrier
-// per step.  Block ids are mapped so that the blocks an XCD runs at one time belong to one layer (ids are
-// dealt to the eight XCDs in turn), so W1_l is shared through that XCD's L2.
+// 128-token blocks would be too few to fill the chip).  Its W1 operands go from global memory to registers,
+// one step ahead: from the tiled copy (TILED) or straight from the rows (a lane loads 32 contiguous bytes of
+// its row per 64-wide step and feeds the halves to two MFMAs).  The token rows are shared by all wavefronts:
+// wavefront j < TT loads token tile j and parks it in LDS in operand order; a fragment half is 4 lane groups
+// of 256 bytes, 16 bytes of padding after each and 64 after the half, which spreads the 8 pieces of a row
+// over 32 banks when they are parked (the reads then see two-way conflicts between lane groups; measured, that
+// costs less than eight-way conflicts on the parking side: 562 against 595 us for 4096 tokens).  Steps go in pairs with one barrier per pair and three pair buffers.  Block ids are mapped so
+// that the blocks an XCD runs at one time belong to one layer (ids are dealt to the eight XCDs in turn), so
+// W1_l is shared through that XCD's L2.
 constexpr int GP_THREADS = 512, GP_HEADS_MAX = 8;
+constexpr int GP_GROUP_BYTES = 272, GP_HALF_BYTES = 4 * GP_GROUP_BYTES, GP_TILE_BYTES = 2 * GP_HALF_BYTES;   // 272, 1088, 2176
 
-template <int HT, int TT>
+template <int HT, int TT, bool TILED>
 __global__ __launch_bounds__(GP_THREADS) void k_gate_prefill(GateView g, const uint16_t* __restrict__ x, int n_tok,
                                                              int layer_begin, int nl, int n_layers, int n_heads, int horizon,
-                                                             const float* __restrict__ v, const float* __restrict__ sconst,
+                                                             const uint4* __restrict__ tiled, const float* __restrict__ v,
+                                                             const float* __restrict__ sconst,
                                                              float* __restrict__ log_beta_out,
                                                              float* __restrict__ log_tail_out) {
     constexpr int GP_TOK = 16 * TT;
-    // [buffer][token tile][half of the step][lane], 4 TT KB; after the loop [wave][head][token] floats, also 4 TT KB
-    __shared__ __align__(16) uint4 s_x[2][TT][2][64];
+    constexpr int STEP_BYTES = TT * GP_TILE_BYTES;
+    // three buffers of [step of the pair][token tile] tiles of 2176 bytes; after the loop [wave][head][token] floats, 4 TT KB
+    __shared__ __align__(16) char s_x[6 * STEP_BYTES];
     const int tid = threadIdx.x, lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);       // uniform: addresses below stay scalar base + lane offset
     const int r16 = lane & 15, g4 = lane >> 4;
@@ -414,14 +457,30 @@ __global__ __launch_bounds__(GP_THREADS) void k_gate_prefill(GateView g, const u
     const int tok0 = (slot % tiles) * GP_TOK;
     const int layer = layer_begin + lr;
     const int hid0 = wave * 16 * HT;
+    const int steps = g.d_model >> 6;                                // 64 contraction indices = 128 bytes of a row per step
 
-    // byte addresses: uniform base + 32-bit lane offset (16 rows of <= 2^20 bytes each)
-    const char* wbase = reinterpret_cast<const char*>(g.w1 + ((size_t)layer * g.d_g + hid0) * g.d_model);
+    // W1: uniform base + 32-bit lane offset, in bytes
     const uint32_t row_bytes = 2u * (uint32_t)g.d_model;
-    const uint32_t aoff = (uint32_t)r16 * row_bytes + 32u * (uint32_t)g4;
-    const int tile_tok0 = tok0 + 16 * min(wave, TT - 1);             // rows past the end repeat the last token, never written
-    const char* xbase = reinterpret_cast<const char*>(x + ((size_t)lr * n_tok + min(tile_tok0, n_tok - 1)) * g.d_model);
-    const uint32_t xoff = (uint32_t)min(r16, max(n_tok - 1 - tile_tok0, 0)) * row_bytes + 32u * (uint32_t)g4;
+    const char* wbase;
+    uint32_t aoff, a_tile_stride;
+    if (TILED) {
+        wbase = reinterpret_cast<const char*>(tiled + ((size_t)lr * (g.d_g >> 4) + (hid0 >> 4)) * steps * 128);
+        aoff = 16u * (uint32_t)lane;
+        a_tile_stride = (uint32_t)steps * 2048u;
+    } else {
+        wbase = reinterpret_cast<const char*>(g.w1 + ((size_t)layer * g.d_g + hid0) * g.d_model);
+        aoff = (uint32_t)r16 * row_bytes + 32u * (uint32_t)g4;
+        a_tile_stride = 16u * row_bytes;
+    }
+    // token rows: lane l takes the 16-byte piece l % 8 of rows l / 8 and l / 8 + 8 of its tile; rows past the end
+    // repeat the last token and are never written
+    const int tile_tok0 = tok0 + 16 * min(wave, TT - 1);
+    const int xr_a = min(tile_tok0 + (lane >> 3), n_tok - 1), xr_b = min(tile_tok0 + (lane >> 3) + 8, n_tok - 1);
+    const char* xbase = reinterpret_cast<const char*>(x + (size_t)lr * n_tok * g.d_model) + 16 * (lane & 7);
+    const size_t xoff_a = (size_t)xr_a * row_bytes, xoff_b = (size_t)xr_b * row_bytes;
+    // where those pieces go inside a parked tile, and where this lane reads its operand from
+    const int park_off = min(wave, TT - 1) * GP_TILE_BYTES + (lane & 1) * GP_HALF_BYTES + ((lane & 7) >> 1) * GP_GROUP_BYTES + (lane >> 3) * 16;
+    const int read_off = g4 * GP_GROUP_BYTES + r16 * 16;
 
     gate_f4 acc[HT][TT];
 #pragma unroll
@@ -429,68 +488,100 @@ __global__ __launch_bounds__(GP_THREADS) void k_gate_prefill(GateView g, const u
 #pragma unroll
         for (int j = 0; j < TT; ++j) acc[i][j] = gate_f4{0.f, 0.f, 0.f, 0.f};
 
-    const int steps = g.d_model >> 6;                                // 64 contraction indices = 128 bytes of a row per step
-    auto col = [&](int kt) { return (size_t)kt * 128; };
-    uint4 a0[HT][2], a1[HT][2], xr0, xr1;
+    uint4 a0[HT][2], a1[HT][2], xr[2][2];
     auto load_a = [&](int kt, uint4 (&a)[HT][2]) {
 #pragma unroll
         for (int i = 0; i < HT; ++i) {
-            const uint4* p = reinterpret_cast<const uint4*>(wbase + (size_t)i * 16 * row_bytes + col(kt) + aoff);
-            a[i][0] = p[0];
-            a[i][1] = p[1];
+            if (TILED) {
+                const uint4* p = reinterpret_cast<const uint4*>(wbase + (size_t)i * a_tile_stride + (size_t)kt * 2048 + aoff);
+                a[i][0] = p[0];
+                a[i][1] = p[64];
+            } else {
+                const uint4* p = reinterpret_cast<const uint4*>(wbase + (size_t)i * a_tile_stride + (size_t)kt * 128 + aoff);
+                a[i][0] = p[0];
+                a[i][1] = p[1];
+            }
         }
     };
     // uniform per wavefront; a compile-time "true" in the full-size variant keeps its loop free of branches
     const bool loader = TT == 8 || wave < TT;
-    xr0 = xr1 = make_uint4(0, 0, 0, 0);
-    auto load_x = [&](int kt) {
+    xr[0][0] = xr[0][1] = xr[1][0] = xr[1][1] = make_uint4(0, 0, 0, 0);
+    auto load_x = [&](int kt) {                                      // the token rows of steps kt and kt + 1
         if (TT == 8 || loader) {
-            const uint4* p = reinterpret_cast<const uint4*>(xbase + col(kt) + xoff);
-            xr0 = p[0];
-            xr1 = p[1];
+            const char* p = xbase + (size_t)kt * 128;
+            xr[0][0] = *reinterpret_cast<const uint4*>(p + xoff_a);
+            xr[0][1] = *reinterpret_cast<const uint4*>(p + xoff_b);
+            xr[1][0] = *reinterpret_cast<const uint4*>(p + xoff_a + 128);
+            xr[1][1] = *reinterpret_cast<const uint4*>(p + xoff_b + 128);
         }
     };
-    auto park_x = [&](int buf) {
+    auto park_x = [&](int buf) {                                     // buf: one of the three pair buffers
         if (TT == 8 || loader) {
-            s_x[buf][wave][0][lane] = xr0;
-            s_x[buf][wave][1][lane] = xr1;
+            char* p = s_x + buf * 2 * STEP_BYTES + park_off;
+            *reinterpret_cast<uint4*>(p) = xr[0][0];
+            *reinterpret_cast<uint4*>(p + 128) = xr[0][1];           // row + 8
+            *reinterpret_cast<uint4*>(p + STEP_BYTES) = xr[1][0];
+            *reinterpret_cast<uint4*>(p + STEP_BYTES + 128) = xr[1][1];
         }
     };
-    auto multiply = [&](int buf, const uint4 (&a)[HT][2]) {
-        uint4 b = s_x[buf][0][0][lane];
+    // One step: 2 TT fragments (fragment f = half f / TT of token tile f % TT), each multiplied into HT accumulator
+    // tiles.  The reads run two fragments ahead of the MFMAs and continue into the next step (`next`), also across
+    // the barrier between pairs, so the matrix pipe does not wait for LDS when a step or a pair begins.
+    uint4 b0, b1;
+    auto frag = [&](const char* base, int f) {
+        return *reinterpret_cast<const uint4*>(base + (f % TT) * GP_TILE_BYTES + (f / TT) * GP_HALF_BYTES);
+    };
+    auto multiply = [&](const char* base, const char* next, const uint4 (&a)[HT][2]) {
 #pragma unroll
-        for (int f = 0; f < 2 * TT; ++f) {                           // fragment f = (half f / TT, token tile f % TT); one read ahead
-            uint4 bn = b;
-            if (f + 1 < 2 * TT) bn = s_x[buf][(f + 1) % TT][(f + 1) / TT][lane];
+        for (int f = 0; f < 2 * TT; ++f) {
+            const uint4 b2 = f + 2 < 2 * TT ? frag(base, f + 2) : frag(next, f + 2 - 2 * TT);
 #pragma unroll
-            for (int i = 0; i < HT; ++i) acc[i][f % TT] = mma_bf16(a[i][f / TT], b, acc[i][f % TT]);
-            b = bn;
+            for (int i = 0; i < HT; ++i) acc[i][f % TT] = mma_bf16(a[i][f / TT], b0, acc[i][f % TT]);
+            b0 = b1;
+            b1 = b2;
             __builtin_amdgcn_sched_barrier(0);                       // keeps the compiler from hoisting all the reads (spills)
         }
     };
+    // Steps go in pairs, the token rows of a pair are parked together, one barrier per pair, three pair buffers.
+    // During pair P: its rows are read from buffer P % 3 (parked during pair P - 2), the rows of pair P + 2 wait in
+    // registers and are parked at the end into buffer (P + 2) % 3 - which pair P - 1 was read from, before the
+    // previous barrier - and the W1 operands of the next step arrive.  The loop has no branches: past the end the
+    // loads repeat the last pair, into registers and buffers nobody reads any more.
+    const int last = steps - 2;                                      // steps is a multiple of 4
     load_x(0);
     load_a(0, a0);
-    park_x(0);
-    __syncthreads();
-    load_x(1);                                                       // x before W1: parking x then waits for its own load only
     load_a(1, a1);
-    // Two steps per trip (steps is a multiple of 4).  The loop body has no branches: past the end the loads
-    // repeat the last step and park it in a buffer nobody reads any more.
-    const int last = steps - 1;
+    park_x(0);
+    load_x(min(2, last));
+    park_x(1);
+    __syncthreads();
+    load_x(min(4, last));
+    int cur = 0;                                                     // buffer of the current pair
+    b0 = frag(s_x + read_off, 0);
+    b1 = frag(s_x + read_off, 1);
     for (int kt = 0; kt < steps; kt += 2) {
-        multiply(0, a0);
-        park_x(1);                                                   // step kt+1; buffer 1 was last read before the previous barrier
-        __syncthreads();
-        load_x(min(kt + 2, last));
+        const int nxt = cur == 2 ? 0 : cur + 1, nn = nxt == 2 ? 0 : nxt + 1;
+        const char* base = s_x + cur * 2 * STEP_BYTES + read_off;
+        multiply(base, base + STEP_BYTES, a0);
         load_a(min(kt + 2, last), a0);
-        multiply(1, a1);
-        park_x(0);
+        multiply(base + STEP_BYTES, s_x + nxt * 2 * STEP_BYTES + read_off, a1);
+        load_a(min(kt + 3, last + 1), a1);
+        park_x(nn);
         __syncthreads();
-        load_x(min(kt + 3, last));
-        load_a(min(kt + 3, last), a1);
+        load_x(min(kt + 6, last));
+        cur = nxt;
     }
 
-    // acc[i][j][r] = pre-activation of (hidden hid0 + 16 i + 4 g4 + r, token tok0 + 16 j + r16)
+    // acc[i][j][r] = pre-activation of (hidden hid0 + 16 i + 4 g4 + r, token tok0 + 16 j + r16).
+    // The folded readout vectors of this layer (heads x d_g floats, at most 16 KB) are fetched while the
+    // activation is applied and staged in LDS behind the [wave][head][token] partial sums.
+    float* s_z = reinterpret_cast<float*>(s_x);                      // every wavefront is past the last barrier of the loop
+    float4* s_v = reinterpret_cast<float4*>(s_x + 4096 * TT);
+    const int v_f4 = (n_heads * g.d_g) >> 2;                         // <= 1024: two per thread
+    const float4* vsrc = reinterpret_cast<const float4*>(v + (size_t)lr * n_heads * g.d_g);
+    float4 v0 = make_float4(0.f, 0.f, 0.f, 0.f), v1 = v0;
+    if (tid < v_f4) v0 = vsrc[tid];
+    if (tid + GP_THREADS < v_f4) v1 = vsrc[tid + GP_THREADS];
 #pragma unroll
     for (int i = 0; i < HT; ++i) {
         const float4 c = *reinterpret_cast<const float4*>(g.c1 + (size_t)layer * g.d_g + hid0 + 16 * i + 4 * g4);
@@ -500,18 +591,20 @@ __global__ __launch_bounds__(GP_THREADS) void k_gate_prefill(GateView g, const u
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const float t = acc[i][j][r] + cc[r];
-                acc[i][j][r] = t / (1.0f + __expf(-t));
+                acc[i][j][r] = t * __builtin_amdgcn_rcpf(1.0f + __expf(-t));   // silu; the reciprocal is good to 1 ulp
             }
     }
-    float* s_z = reinterpret_cast<float*>(&s_x[0][0][0][0]);         // every wavefront is past the last barrier of the loop
+    if (tid < v_f4) s_v[tid] = v0;
+    if (tid + GP_THREADS < v_f4) s_v[tid + GP_THREADS] = v1;
+    __syncthreads();
     for (int h = 0; h < n_heads; ++h) {
-        const float* vh = v + ((size_t)lr * n_heads + h) * g.d_g + hid0 + 4 * g4;
+        const float4* vh = s_v + ((h * g.d_g + hid0) >> 2) + g4;
         float zp[TT];
 #pragma unroll
         for (int j = 0; j < TT; ++j) zp[j] = 0.f;
 #pragma unroll
         for (int i = 0; i < HT; ++i) {
-            const float4 w = *reinterpret_cast<const float4*>(vh + 16 * i);
+            const float4 w = vh[4 * i];
             const float ww[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
             for (int j = 0; j < TT; ++j)
@@ -543,7 +636,7 @@ __global__ __launch_bounds__(GP_THREADS) void k_gate_prefill(GateView g, const u
 
 // Below this many tokens the fold's extra pass over W2 and the few blocks of the prefill kernel do not pay.
 #ifndef KVTRIM_GATE_PREFILL_MIN_TOK
-#define KVTRIM_GATE_PREFILL_MIN_TOK 256
+#define KVTRIM_GATE_PREFILL_MIN_TOK 128
 #endif
 constexpr int GP_MIN_TOK = KVTRIM_GATE_PREFILL_MIN_TOK;
 
@@ -556,11 +649,23 @@ kvtrim_status launch_gate(kvtrim_ctx* ctx, const GateView& g, const uint16_t* x,
     const int nl = layer_end - layer_begin;
     const int n_heads = ctx->shape.n_kv_heads;
     if (n_tok >= GP_MIN_TOK && prefill_shape(ctx, g)) {
-        float* v = scratch;                                          // [nl][heads][d_g]
-        float* sconst = scratch + (size_t)nl * n_heads * g.d_g;      // [nl][heads]
+        // scratch: v [nl][heads][d_g], s [nl][heads], then (16-byte aligned) the tiled copy of W1 if the buffer
+        // - n_tok * nl * d_g floats - has room for it, which also means the call is long enough for the pass to pay
+        float* v = scratch;
+        float* sconst = scratch + (size_t)nl * n_heads * g.d_g;
+        const size_t fold_floats = ((size_t)nl * n_heads * (g.d_g + 1) + 3) & ~(size_t)3;
+        const size_t tiled_floats = (size_t)nl * g.d_g * g.d_model / 2;
+        const bool use_tiled = fold_floats + tiled_floats <= (size_t)n_tok * nl * g.d_g;
+        uint4* tiled = reinterpret_cast<uint4*>(scratch + fold_floats);
         {
             ProfScope prof(ctx, K_GATE_FOLD, st);
             hipLaunchKernelGGL(k_gate_fold, dim3(n_heads, nl), dim3(GF_THREADS), 0, st, g, layer_begin, n_heads, v, sconst);
+        }
+        if (use_tiled) {
+            ProfScope prof(ctx, K_GATE_RETILE, st);
+            const int steps = g.d_model >> 6;
+            hipLaunchKernelGGL(k_gate_retile, dim3((steps / 4 + GT_THREADS / 64 - 1) / (GT_THREADS / 64), g.d_g / 16, nl),
+                               dim3(GT_THREADS), 0, st, g, layer_begin, tiled);
         }
         {
             ProfScope prof(ctx, K_GATE_PREFILL, st);
@@ -569,14 +674,15 @@ kvtrim_status launch_gate(kvtrim_ctx* ctx, const GateView& g, const uint16_t* x,
             while (tt > 2 && (int64_t)nl * ((n_tok + 16 * tt - 1) / (16 * tt)) < 256) tt >>= 1;
             const int tiles = (n_tok + 16 * tt - 1) / (16 * tt);
             const dim3 grid(8u * (unsigned)((nl + 7) / 8) * (unsigned)tiles);
-#define KVTRIM_GATE_PREFILL(HT, TT)                                                                                           \
-    hipLaunchKernelGGL((k_gate_prefill<HT, TT>), grid, dim3(GP_THREADS), 0, st, g, x, n_tok, layer_begin, nl,                 \
-                       ctx->shape.n_layers, n_heads, horizon, v, sconst, log_beta_out, log_tail_out)
+#define KVTRIM_GATE_PREFILL(HT, TT, TILED)                                                                                    \
+    hipLaunchKernelGGL((k_gate_prefill<HT, TT, TILED>), grid, dim3(GP_THREADS), 0, st, g, x, n_tok, layer_begin, nl,          \
+                       ctx->shape.n_layers, n_heads, horizon, tiled, v, sconst, log_beta_out, log_tail_out)
 #define KVTRIM_GATE_PREFILL_TT(HT)                                                                                            \
     do {                                                                                                                      \
-        if (tt == 8) KVTRIM_GATE_PREFILL(HT, 8);                                                                              \
-        else if (tt == 4) KVTRIM_GATE_PREFILL(HT, 4);                                                                         \
-        else KVTRIM_GATE_PREFILL(HT, 2);                                                                                      \
+        if (use_tiled) KVTRIM_GATE_PREFILL(HT, 8, true);       /* room for the tiled copy implies 128-token blocks */         \
+        else if (tt == 8) KVTRIM_GATE_PREFILL(HT, 8, false);                                                                  \
+        else if (tt == 4) KVTRIM_GATE_PREFILL(HT, 4, false);                                                                  \
+        else KVTRIM_GATE_PREFILL(HT, 2, false);                                                                               \
     } while (0)
             switch (g.d_g / 128) {
                 case 1: KVTRIM_GATE_PREFILL_TT(1); break;

@@ -65,6 +65,7 @@ def rel_err(got, ref):
     (9, 2, 256, 256, 16, 260),        # ... nine layers: the second round of the layer-to-XCD dealing is partly empty
     (1, 8, 256, 384, 5, 513),         # ... eight heads, three tiles per wavefront, token tail of one
     (3, 2, 256, 512, 1, 256),         # ... exactly two full token tiles, scalar projection
+    (2, 2, 512, 128, 9, 129),         # ... just above the switch-over: 32-token blocks, a tail of one
 ])
 def test_gate_forward_matches_the_oracle(L, H, d_model, d_g, d_p, n_tok):
     z_ref, lb_ref, _, lb, _ = run_both(L, H, d_model, d_g, d_p, n_tok, salt=d_p)
@@ -91,7 +92,7 @@ def test_horizon_tail_constant(horizon):
 
 
 def test_prefill_sized_call_with_a_layer_range_and_a_horizon():
-    # the folded path (256 tokens and more): layers outside the range stay untouched, the tail constant follows log beta
+    # the folded path (128 tokens and more): layers outside the range stay untouched, the tail constant follows log beta
     _, lb_ref, lt_ref, lb, lt = run_both(5, 2, 256, 128, 12, 300, b_g=1.0, layer_begin=1, layer_end=4, horizon=2)
     assert np.isnan(lb[:, 0, :]).all() and np.isnan(lb[:, 4, :]).all()
     assert np.isnan(lt[:, 0, :]).all() and np.isnan(lt[:, 4, :]).all()
@@ -100,16 +101,16 @@ def test_prefill_sized_call_with_a_layer_range_and_a_horizon():
 
 
 def test_both_paths_agree_across_the_token_threshold():
-    # 255 tokens run the per-token kernels, 256 the folded ones: the shared 255 tokens get the same gates to rounding
+    # 127 tokens run the per-token kernels, 128 the folded ones: the shared 127 tokens get the same gates to rounding
     L, H, d_model, d_g, d_p = 2, 2, 512, 256, 24
     w = ki.gate_weights(L, H, d_model, d_g, d_p, b_g=3.5, seed=77)
-    x = ki.gate_inputs(L, 256, d_model, salt=3)
+    x = ki.gate_inputs(L, 128, d_model, salt=3)
     og = oracle.Gate(bf16_bits(w["w1"]), w["c1"].numpy(), bf16_bits(w["w2"]), w["c2"].numpy(), w["w_g"].numpy(), 3.5)
     _, lb_ref, _ = oracle.gate_forward(og, bf16_bits(x), 0, L, None)
     ctx = kv.Context(1, L, H, H, 64, 1024)
     gate = kv.Gate.from_dict(w, DEV)
     got = {}
-    for n_tok in (255, 256):
+    for n_tok in (127, 128):
         xd = x[:, :n_tok].contiguous().to(DEV)
         scratch = torch.empty(kv.kvtrim_gate_scratch_bytes(gate, n_tok, L) // 4, dtype=torch.float32, device=DEV)
         lb = torch.full((n_tok, L, H), float("nan"), dtype=torch.float32, device=DEV)
@@ -117,7 +118,7 @@ def test_both_paths_agree_across_the_token_threshold():
         assert kv.kvtrim_poll_error(ctx) == 0
         got[n_tok] = lb.cpu().numpy()
         assert rel_err(got[n_tok], lb_ref[:n_tok]) <= RTOL
-    assert np.max(np.abs(got[255] - got[256][:255]) / np.abs(lb_ref[:255])) <= RTOL
+    assert np.max(np.abs(got[127] - got[128][:127]) / np.abs(lb_ref[:127])) <= RTOL
 
 
 def test_initial_bias_of_eighteen_keeps_beta_next_to_one():
