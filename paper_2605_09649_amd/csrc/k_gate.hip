@@ -16,6 +16,7 @@
 //                   (u = hi + lo to 2^-17 relative) so that the second layer keeps fp32-like
 //                   accuracy on the bf16 matrix cores; every wavefront takes 16-row tiles of W2,
 //                   folds its rows with w_g, and the block adds b_g and applies log-sigmoid.
+//   k_gate_fold, k_gate_retile, k_gate_prefill   calls of 128 tokens and more: see further down.
 // The contraction index may be permuted freely as long as both operands use the same permutation:
 // a lane loads 32 contiguous bytes of its row per 64-wide step (so four lanes read one full
 // 128-byte line) and feeds the two halves to two MFMAs.
@@ -117,17 +118,13 @@ __global__ __launch_bounds__(GH_THREADS) void k_gate_hidden(GateView g, const ui
     }
 }
 
-// The same first layer for many tokens (prefill, chunked prefill): a 128 x 128 output tile per block,
-// 64-wide steps of both operands staged through LDS (the next step's global loads are in flight in
-// registers while the current one is multiplied), 2 x 2 wavefronts of 64 x 64, i.e. 4 x 4 MFMA tiles
-// each.  Both operands are contiguous along the contraction, so global loads, LDS rows and MFMA
-// operands all use the same 16-byte pieces; LDS rows are padded by 16 bytes against bank conflicts.
-// Measured (4096 tokens, the metric model): 175 TFLOP/s, 7 % of the MFMA peak - the matrix pipe is busy 7 % of
-// the time and the L2 misses fetch 10.8 GB for 1.2 GB of distinct operands (a 128-token tile is shared by only
-// four blocks, and the 4 MB of W1_l do not stay in a 4 MB L2 while tokens stream through it).  Re-mapping blocks
-// so that a layer stays on one XCD, a second register stage, and rotating the start of the contraction per block
-// changed nothing or made it slower; the fix is a tile that spans all rows of W1_l.  Not built: this kernel only
-// serves prefill-sized calls, which are not on the decode path.
+// The first layer alone for many tokens when the hidden width does not fit the folded prefill kernel below
+// (not a multiple of 128, or above 512): a 128 x 128 output tile per block, 64-wide steps of both operands
+// staged through LDS (the next step's global loads are in flight in registers while the current one is
+// multiplied), 2 x 2 wavefronts of 64 x 64, i.e. 4 x 4 MFMA tiles each.  Both operands are contiguous along
+// the contraction, so global loads, LDS rows and MFMA operands all use the same 16-byte pieces; LDS rows are
+// padded by 16 bytes against bank conflicts.  Measured (4096 tokens, the metric model): 175 TFLOP/s, 7 % of the
+// MFMA peak - a 128-token tile is shared by only four blocks and every block re-reads its W1 rows.
 constexpr int GG_BM = 128, GG_BN = 128, GG_BK = 64, GG_LD = GG_BK + 8;
 
 __global__ __launch_bounds__(256) void k_gate_hidden_gemm(GateView g, const uint16_t* __restrict__ x, int n_tok,
