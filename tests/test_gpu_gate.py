@@ -66,6 +66,8 @@ def rel_err(got, ref):
     (1, 8, 256, 384, 5, 513),         # ... eight heads, three tiles per wavefront, token tail of one
     (3, 2, 256, 512, 1, 256),         # ... exactly two full token tiles, scalar projection
     (2, 2, 512, 128, 9, 129),         # ... just above the switch-over: 32-token blocks, a tail of one
+    (2, 2, 256, 512, 16, 300),        # ... the paper's hidden width from the tiled copy of W1 (short rows: the copy fits the scratch)
+    (32, 2, 1280, 128, 8, 520),       # ... 64-token blocks (32 layers x 9 tiles), W1 straight from its rows
 ])
 def test_gate_forward_matches_the_oracle(L, H, d_model, d_g, d_p, n_tok):
     z_ref, lb_ref, _, lb, _ = run_both(L, H, d_model, d_g, d_p, n_tok, salt=d_p)

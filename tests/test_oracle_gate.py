@@ -150,3 +150,18 @@ def test_synthetic_gate_has_the_spread_of_the_workload_logits():
     z, lb, _ = oracle.gate_forward(g, bf16_bits(ki.gate_inputs(4, 64, 256)))
     assert abs(z.mean() - 3.5) < 1.0 and 0.8 < z.std() < 2.5
     assert (lb < 0).all()
+
+
+def test_second_layer_and_readout_collapse_to_one_vector_per_gate():
+    # Sec. 4.1 as read here has no nonlinearity between the second layer of Proj and the tied readout, so
+    # z = w_g . (W2 u + c2) + b_g = (W2^T w_g) . u + (w_g . c2 + b_g) exactly.  The HIP path uses this for long
+    # calls; here the oracle's nested sums are checked against the collapsed form written with library routines.
+    w, g = make_gate(L=2, H=3, d_model=64, d_g=24, d_p=9, b_g=-0.375, seed=5)
+    x = ki.gate_inputs(2, 6, 64, salt=2)
+    z, _, _ = oracle.gate_forward(g, bf16_bits(x))
+    for layer in range(2):
+        u = F.silu(F.linear(x[layer].double(), w["w1"][layer].double(), w["c1"][layer].double()))
+        for h in range(3):
+            v = w["w2"][layer, h].double().T @ w["w_g"].double()
+            s = w["w_g"].double() @ w["c2"][layer, h].double() + w["b_g"]
+            assert np.allclose(z[:, layer, h], (u @ v + s).numpy(), rtol=1e-12, atol=1e-12)
