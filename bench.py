@@ -149,6 +149,93 @@ def bench_gate(args):
     print(json.dumps(result), flush=True)
 
 
+def bench_chunk(args):
+    """The chunked-prefill step of the multi-turn workload: every segment of all 16 sequences takes a chunk of
+    CHUNK new tokens, then the cache is rescored, selected and compacted back to the per-sequence budgets (no
+    attention in this step).  Starts from empty caches; the cache is at its budget after two chunks, the timed
+    steps come after that.  One JSON line of its own; parity of this flow is covered by the GPU tests."""
+    import numpy as np
+    import torch
+    import kvtrim_inputs as ki
+    import paper_2605_09649_amd as kv
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = ki.workload("multiturn")
+    chunk, K = args.chunk, args.steps
+    W = max(args.warmup, -(-max(w.budget) // (chunk * w.n_layers * w.n_kv_heads)) + 1)   # past the fill-up phase
+    nseg, D, S = w.nseg, w.head_dim, w.n_seq
+    per_seq = w.n_layers * w.n_kv_heads
+    reserve = chunk
+    B = sum(w.budget)
+    cap = B + nseg * reserve + 8
+    caches = [kv.Cache.empty(nseg, D, cap, dev) for _ in range(2)]
+    caches[0].seg_start.copy_(torch.arange(nseg, dtype=torch.int64) * reserve)
+    ctx = kv.Context(S, w.n_layers, w.n_kv_heads, w.n_q_heads, D, cap)
+    score = torch.zeros(cap, dtype=torch.float32, device=dev)
+    keep = torch.zeros(cap, dtype=torch.uint8, device=dev)
+    kept = torch.zeros(nseg, dtype=torch.int32, device=dev)
+    thr = torch.zeros(S, dtype=torch.int32, device=dev)
+    budget = torch.tensor(list(w.budget), dtype=torch.int64, device=dev)
+    t0 = time.time()
+    inp = ki.chunk_inputs(w, chunk, dev)                            # the same K / V / log beta rows every step; positions move on
+    torch.cuda.synchronize()
+    log(f"[bench] chunk of {chunk} tokens x {nseg} segments: {2 * nseg * chunk * D * 2 / 1e9:.2f} GB of new K/V, "
+        f"generated in {time.time() - t0:.1f}s")
+    ar = torch.arange(chunk, dtype=torch.int32, device=dev)
+    pos_news = [(ar + s * chunk).repeat(nseg, 1).contiguous() for s in range(W + K)]
+    nows = [torch.full((S,), (s + 1) * chunk - 1, dtype=torch.int32, device=dev) for s in range(W + K)]
+    state = {"cur": 0}
+
+    def step(s):
+        cur, dst = caches[state["cur"]], caches[state["cur"] ^ 1]
+        kv.kvtrim_append(ctx, cur, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos_news[s], chunk)
+        kv.kvtrim_score(ctx, cur, nows[s], score)
+        kv.kvtrim_select_global(ctx, cur, score, budget, keep, kept, thr)
+        kv.kvtrim_compact(ctx, cur, keep, kept, dst, reserve)
+        state["cur"] ^= 1
+
+    for s in range(W):
+        step(s)
+    torch.cuda.synchronize()
+    assert kv.kvtrim_poll_error(ctx) == 0, "device-side error while the caches filled up"
+    n_ret = int(kept.sum().item())
+    n_cand = n_ret + nseg * chunk
+    kv.kvtrim_profile_begin(ctx, (1 << kv.binding.N_KERNELS) - 1)
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for s in range(W, W + K):
+        step(s)
+    torch.cuda.synchronize()
+    t_end = time.perf_counter()
+    prof = kv.kvtrim_profile_end(ctx)
+    assert kv.kvtrim_poll_error(ctx) == 0, "device-side error in the timed region"
+    assert int(kept.sum().item()) == n_ret == B
+    ms = (t_end - t_begin) * 1e3 / K
+    for name, (t, n) in sorted(prof.items(), key=lambda kvp: -kvp[1][0]):
+        log(f"[bench]   {name:16s} {t / n * 1e3:8.1f} us x {n}")
+    R = 4 * D + 8
+    stage = {"append": 2 * R * nseg * chunk, "score": 8 * n_cand, "select": 5 * n_cand, "compact": 2 * R * n_ret}
+    total = sum(stage.values())
+    dom = "k_cmp_copy"
+    d_ms = prof[dom][0] / prof[dom][1]
+    log(f"[bench] chunk step: {ms:.3f} ms ({total / (ms * 1e-3) / 1e9:.0f} GB/s algorithmic end to end); {dom} {d_ms:.3f} ms "
+        f"({stage['compact'] / (d_ms * 1e-3) / 1e9:.0f} GB/s)")
+    print(json.dumps({
+        "metric": "chunked-prefill steps/sec (append a chunk, rescore, select, compact), 16 sequences", "value": 1e3 / ms,
+        "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"multiturn chunk step: S{S} L{w.n_layers} Hkv{w.n_kv_heads} D{D}, {chunk} new tokens per "
+                               f"segment, {n_cand} candidates -> {n_ret} retained per step",
+                   "stages": "append, score, select_global, compact (no attention in a chunk step)"},
+        "end_to_end": {"algorithmic_bytes_per_step": total, "achieved_GBps": total / (ms * 1e-3) / 1e9,
+                       "frac_of_hbm_peak": total / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "bytes_by_stage": stage},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": stage["compact"] / (d_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": stage["compact"] / (d_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": stage["compact"], "avg_launch_ms": d_ms},
+    }), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -175,7 +262,17 @@ def main():
     ap.add_argument("--gate", type=int, default=0, metavar="N_TOK",
                     help="time the retention-gate forward alone (the metric model's shape: 32 layers x 8 KV heads, "
                          "d_model 4096, hidden width 512, projection width 128) for N_TOK tokens per call")
+    ap.add_argument("--chunk", type=int, default=0, metavar="N_TOK",
+                    help="time the chunked-prefill step of the multi-turn workload instead of decode steps: N_TOK new "
+                         "tokens per segment, then rescore, select, compact (the paper-shaped chunk is 4096)")
     args = ap.parse_args()
+    if args.chunk:
+        if args.gpus != 1:
+            print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+            sys.exit(2)
+        if not 1 <= args.chunk <= 4096:
+            ap.error("--chunk takes 1 .. 4096 tokens")
+        return bench_chunk(args)
     if args.gate:
         if args.gpus != 1:
             print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
