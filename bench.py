@@ -253,6 +253,8 @@ def main():
     ap.add_argument("--paged", action="store_true",
                     help="steady state on the paged layout: eviction frees slots of fixed-size pages and moves no K/V "
                          "(paged_append, paged_score, paged_select, paged_evict, paged_attn)")
+    ap.add_argument("--defrag-every", type=int, default=0, metavar="N",
+                    help="with --paged: defragment the pages every N steps (kvtrim_paged_defrag), inside the timed region")
     ap.add_argument("--kernel-times", action="store_true",
                     help="bracket every kernel with HIP events and print the per-kernel averages to stderr "
                          "(the events add a little to ms_per_step)")
@@ -280,6 +282,8 @@ def main():
         return bench_gate(args)
     if args.paged and args.unfused:
         ap.error("--paged and --unfused exclude each other")
+    if args.defrag_every and not args.paged:
+        ap.error("--defrag-every needs --paged")
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
@@ -349,6 +353,8 @@ def main():
             kv.kvtrim_paged_score(ctx, pc, nows[s], score)
             kv.kvtrim_paged_select(ctx, pc, score, budget, keep, kept, thr)
             kv.kvtrim_paged_evict(ctx, pc, keep)
+            if args.defrag_every and s % args.defrag_every == 0:
+                kv.kvtrim_paged_defrag(ctx, pc)
             kv.kvtrim_paged_attn(ctx, pc, inp["q"], 0, w.n_layers, scale, out, lse)
             return
         kv.kvtrim_append(ctx, cur, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos_news[s], 1,

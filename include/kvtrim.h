@@ -268,6 +268,17 @@ kvtrim_status kvtrim_paged_select(kvtrim_ctx *ctx, const kvtrim_paged_cache *c, 
  * live entry return to the free list and leave their segment's block table.  No K/V moves. */
 kvtrim_status kvtrim_paged_evict(kvtrim_ctx *ctx, kvtrim_paged_cache *c, const uint8_t *keep, void *hip_stream);
 
+/* Housekeeping of the paged layout (Sec. 4.2 "Implementation details" describes the layout; the paper does not
+ * discuss fragmentation): eviction frees a page only when all of its slots are empty, so over many steps a
+ * segment spreads over more pages than its live entries need.  For every segment whose live entries fit into
+ * fewer pages, the last pages of its block table are emptied into the free slots of the pages before them
+ * (K row, V row, log beta, position and tail constant move together) and return to the free list; afterwards
+ * the segment holds ceil(live / KVTRIM_PAGE_SIZE) pages.  The set of entries of every segment is unchanged (a
+ * segment's entries have no order inside its pages), so scores, selections and attention outputs are the same
+ * as without the call, up to the order of floating-point sums in attention.  Call it when the pool runs low
+ * or every few hundred steps; a segment that is already tight costs one look at its page counts. */
+kvtrim_status kvtrim_paged_defrag(kvtrim_ctx *ctx, kvtrim_paged_cache *c, void *hip_stream);
+
 /* Stage 4 on the paged layout: as kvtrim_decode_attn, over the live slots of each segment's pages. */
 kvtrim_status kvtrim_paged_attn(kvtrim_ctx *ctx, const kvtrim_paged_cache *c, const void *q, int32_t layer_begin,
                                 int32_t layer_end, float softmax_scale, float *out, float *lse, void *hip_stream);
@@ -328,7 +339,7 @@ kvtrim_status kvtrim_gate_forward(kvtrim_ctx *ctx, const kvtrim_gate *g, const v
  * end waits for `hip_stream` and writes, per kernel id, the summed duration in
  * milliseconds and the number of bracketed launches into host arrays of
  * KVTRIM_N_KERNELS elements.  Do not capture a HIP graph while profiling is on. */
-#define KVTRIM_N_KERNELS 28
+#define KVTRIM_N_KERNELS 29
 #define KVTRIM_PROFILE_MAX_LAUNCHES 4096
 kvtrim_status kvtrim_profile_begin(kvtrim_ctx *ctx, uint32_t kernel_mask);
 kvtrim_status kvtrim_profile_end(kvtrim_ctx *ctx, void *hip_stream, double *ms_sum_host,

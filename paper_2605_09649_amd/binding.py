@@ -15,11 +15,11 @@ EXPORTS = ["kvtrim_create", "kvtrim_destroy", "kvtrim_workspace_bytes", "kvtrim_
            "kvtrim_poll_error", "kvtrim_score", "kvtrim_select_global", "kvtrim_compact",
            "kvtrim_decode_attn", "kvtrim_decode_attn_soft", "kvtrim_occupancy", "kvtrim_compact_attn", "kvtrim_append",
            "kvtrim_paged_build", "kvtrim_paged_append", "kvtrim_paged_score", "kvtrim_paged_select",
-           "kvtrim_paged_evict", "kvtrim_paged_attn", "kvtrim_gate_scratch_bytes", "kvtrim_gate_forward",
+           "kvtrim_paged_evict", "kvtrim_paged_defrag", "kvtrim_paged_attn", "kvtrim_gate_scratch_bytes", "kvtrim_gate_forward",
            "kvtrim_profile_begin", "kvtrim_profile_end",
            "kvtrim_kernel_name"]
 PAGE_SIZE = 128
-N_KERNELS = 28
+N_KERNELS = 29
 
 
 class KvtrimError(RuntimeError):
@@ -93,6 +93,7 @@ def load_library():
         lib.kvtrim_paged_select.argtypes = [C.c_void_p, P, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                             C.c_void_p]
         lib.kvtrim_paged_evict.argtypes = [C.c_void_p, P, C.c_void_p, C.c_void_p]
+        lib.kvtrim_paged_defrag.argtypes = [C.c_void_p, P, C.c_void_p]
         lib.kvtrim_paged_attn.argtypes = [C.c_void_p, P, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p,
                                           C.c_void_p, C.c_void_p]
         lib.kvtrim_gate_scratch_bytes.argtypes = [C.POINTER(_Gate), C.c_int32, C.c_int32]
@@ -334,6 +335,10 @@ def kvtrim_paged_select(ctx, cache, score, budget, keep_out, kept_out, thr_key_o
 def kvtrim_paged_evict(ctx, cache, keep, stream=None):
     _check(ctx, load_library().kvtrim_paged_evict(ctx.handle, C.byref(cache.c), _ptr(keep, torch.uint8),
                                                   _stream(stream)), "kvtrim_paged_evict")
+
+
+def kvtrim_paged_defrag(ctx, cache, stream=None):
+    _check(ctx, load_library().kvtrim_paged_defrag(ctx.handle, C.byref(cache.c), _stream(stream)), "kvtrim_paged_defrag")
 
 
 def kvtrim_paged_attn(ctx, cache, q, layer_begin, layer_end, softmax_scale, out, lse=None, stream=None):

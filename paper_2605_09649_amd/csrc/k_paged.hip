@@ -759,6 +759,108 @@ __global__ __launch_bounds__(256) void k_pg_tidy(PagedView pc, int32_t* err) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Defragmentation (housekeeping of the paged layout, not a step of the method): eviction frees a page only
+// when all of its slots are empty, so a segment slowly spreads over more pages than its live entries need.
+// One block per segment: if the live entries fit into fewer pages, the last pages of the block table are
+// emptied into the free slots of the pages before them - K row, V row, log beta, position, tail constant
+// move together - and return to the free list; the table is cut.  A segment's entries have no order inside
+// its pages, so nothing else changes; segments that are already as tight as they can be are left alone.
+// Works in passes of at most PGD_LIST moves: whole pages of entries to move (from the table's end backwards)
+// and the free slots that take them (from its start forwards) are listed in LDS, then every wavefront
+// moves one entry at a time.
+constexpr int PGD_THREADS = 256, PGD_LIST = 1024;
+
+__global__ __launch_bounds__(PGD_THREADS) void k_pg_defrag(PagedView pc, int head_dim, int32_t* err) {
+    __shared__ int32_t lds32[17];
+    __shared__ int64_t s_from[PGD_LIST], s_to[PGD_LIST];
+    __shared__ int s_bad;
+    const int g = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    const int npg = pc.seg_pages[g];
+    if (npg < 0 || npg > pc.max_pps) {
+        if (tid == 0) atomicOr(err, ERR_LAYOUT);
+        return;
+    }
+    if (npg == 0) return;
+    int32_t* bt = pc.block_table + (int64_t)g * pc.max_pps;
+    if (tid == 0) s_bad = 0;
+    __syncthreads();
+    int mine = 0;
+    for (int i = tid; i < npg; i += PGD_THREADS) {
+        const int page = bt[i];
+        if (page < 0 || page >= pc.n_pages || pc.page_owner[page] != g) s_bad = 1;
+        else mine += pc.page_live[page];
+    }
+    const int total = block_sum<int32_t>(mine, lds32);               // its barriers also publish s_bad
+    if (s_bad || total < 0 || total > npg * P) {
+        if (tid == 0) atomicOr(err, ERR_LAYOUT);
+        return;
+    }
+    const int keep_pages = (total + P - 1) / P;
+    if (keep_pages >= npg) return;                                   // as tight as it can be
+
+    const int words = head_dim >> 1;                                 // 32-bit words of a K or V row
+    uint32_t* k32 = reinterpret_cast<uint32_t*>(pc.k);
+    uint32_t* v32 = reinterpret_cast<uint32_t*>(pc.v);
+    int rc = 0;                                                      // next page that may still have free slots
+    int dc = npg - 1;                                                // next page to empty
+    while (dc >= keep_pages) {                                       // every quantity that steers the loops is the same in all threads
+        // entries to move: whole pages while the list has room for one more
+        int nf = 0;
+        while (dc >= keep_pages && nf + P <= PGD_LIST) {
+            const int page = bt[dc];
+            const int64_t e = (int64_t)page * P + tid;
+            const bool live = tid < P && pc.pos[e] >= 0;
+            int32_t tot;
+            const int32_t ex = block_excl_scan<int32_t>(live ? 1 : 0, lds32, &tot);
+            if (live) s_from[nf + ex] = e;
+            nf += tot;
+            --dc;
+        }
+        // as many free slots of the pages that stay
+        int nh = 0;
+        while (nh < nf && rc < keep_pages) {
+            const int page = bt[rc];
+            const int64_t e = (int64_t)page * P + tid;
+            const bool hole = tid < P && pc.pos[e] < 0;
+            int32_t tot;
+            const int32_t ex = block_excl_scan<int32_t>(hole ? 1 : 0, lds32, &tot);
+            if (hole && nh + ex < nf) s_to[nh + ex] = e;
+            if (nh + tot <= nf) ++rc;                                // the page is full after this pass
+            nh = min(nf, nh + tot);
+        }
+        if (nh < nf) {                                               // the live counts did not describe the pages
+            if (tid == 0) atomicOr(err, ERR_MISMATCH);
+            return;
+        }
+        __syncthreads();
+        for (int m = wave; m < nf; m += PGD_THREADS / 64) {
+            const int64_t src = s_from[m], dst = s_to[m];
+            for (int i = lane; i < words; i += 64) {
+                k32[dst * words + i] = k32[src * words + i];
+                v32[dst * words + i] = v32[src * words + i];
+            }
+            if (lane == 0) {
+                pc.log_beta[dst] = pc.log_beta[src];
+                if (pc.log_tail) pc.log_tail[dst] = pc.log_tail[src];
+                pc.pos[dst] = pc.pos[src];
+                pc.pos[src] = -1;
+                atomicAdd(&pc.page_live[(int)(dst / P)], 1);
+                atomicSub(&pc.page_live[(int)(src / P)], 1);
+            }
+        }
+        __syncthreads();                                             // the next pass looks at the slots again
+    }
+    for (int i = keep_pages + tid; i < npg; i += PGD_THREADS) {     // the emptied pages go back to the free list
+        const int page = bt[i];
+        pc.page_owner[page] = -1;
+        pc.page_live[page] = 0;
+        const int idx = atomicAdd(pc.n_free, 1);
+        if (idx >= 0 && idx < pc.n_pages) pc.free_list[idx] = page;
+    }
+    if (tid == 0) pc.seg_pages[g] = keep_pages;
+}
+
+// ---------------------------------------------------------------------------------------------
 static PagedView view_of(const kvtrim_paged_cache* c) {
     PagedView v;
     v.k = (uint16_t*)c->k;
@@ -940,6 +1042,19 @@ kvtrim_status kvtrim_paged_evict(kvtrim_ctx* ctx, kvtrim_paged_cache* c, const u
     {
         ProfScope prof(ctx, K_PG_TIDY, st);
         hipLaunchKernelGGL(k_pg_tidy, dim3(ctx->shape.nseg), dim3(256), 0, st, pv, ctx->ws.err);
+    }
+    KVTRIM_HIP(ctx, hipGetLastError());
+    return KVTRIM_OK;
+}
+
+kvtrim_status kvtrim_paged_defrag(kvtrim_ctx* ctx, kvtrim_paged_cache* c, void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    if (const char* p = paged_problem(ctx, c)) return bad(ctx, p);
+    hipStream_t st = (hipStream_t)hip_stream;
+    {
+        ProfScope prof(ctx, K_PG_DEFRAG, st);
+        hipLaunchKernelGGL(k_pg_defrag, dim3(ctx->shape.nseg), dim3(PGD_THREADS), 0, st, view_of(c), ctx->shape.head_dim,
+                           ctx->ws.err);
     }
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;

@@ -137,10 +137,11 @@ def ties_overflow(w, hc, score_ref, live, thr_ref, budget_np):
 
 
 def run_paged_both(w, budgets, device="cuda:0", cache_dict=None, now0=None, n_pages=None, max_pps=None, horizon=1,
-                   tweak_new=None):
+                   tweak_new=None, defrag_at=()):
     """budgets: one per-sequence budget list per step; step 0 selects on the ragged prefill cache
     and builds the pages, the later steps run on the pages.  tweak_new(step, inputs) may edit the
-    generated inputs of a step (used to plant ties).  Returns one dict of findings per step."""
+    generated inputs of a step (used to plant ties).  In the steps listed in defrag_at the pages are
+    defragmented between eviction and attention.  Returns one dict of findings per step."""
     reserve = 1
     if cache_dict is None:
         cache_dict = ki.prefill_cache(w, reserve=reserve)
@@ -213,6 +214,14 @@ def run_paged_both(w, budgets, device="cuda:0", cache_dict=None, now0=None, n_pa
                                                               score_ref[live].view(np.uint32)))
             res["keep_equal"] = bool(same and np.array_equal(keep.cpu().numpy()[idx], keep_ref[live]))
             kv.kvtrim_paged_evict(ctx, pc, keep)
+        if step in defrag_at:
+            before = PagedHost(pc, rows=False)
+            kv.kvtrim_paged_defrag(ctx, pc)
+            after = PagedHost(pc, rows=False)
+            res["defrag"] = {"pages_before": int(before.seg_pages.sum()), "pages_after": int(after.seg_pages.sum()),
+                             "tight": bool(np.array_equal(after.seg_pages, (after.seg_live + P - 1) // P)),
+                             "live_unchanged": bool(np.array_equal(before.seg_live, after.seg_live)),
+                             "free_gain": after.n_free - before.n_free}
         kv.kvtrim_paged_attn(ctx, pc, d["q"], 0, w.n_layers, scale, out, lse)
         res["status"] = kv.kvtrim_poll_error(ctx)
         res["kept_equal"] = bool(np.array_equal(kept.cpu().numpy(), kept_ref)

@@ -246,3 +246,50 @@ def test_chunk_append_without_pages_leaves_the_segment_unchanged():
     assert list(after.seg_live) == [250, 140] and after.n_free == 1   # segment 1 filled its hole and took one page
     with pytest.raises(kv.KvtrimError):
         kv.kvtrim_paged_append(ctx, pc, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos.to(DEV), n_new=5000)
+
+
+def check_defrag(results, steps_with_defrag, must_free=True):
+    for r in results:
+        if r["step"] in steps_with_defrag:
+            d = r["defrag"]
+            assert d["tight"] and d["live_unchanged"], d
+            assert d["free_gain"] == d["pages_before"] - d["pages_after"] >= 0, d
+            if must_free:
+                assert d["pages_after"] < d["pages_before"], d
+
+
+def test_defragmentation_packs_every_segment_into_the_fewest_pages():
+    # the budget drops to a third after the pages were built with everything kept: holes all over the pages; the
+    # defragmented pool holds ceil(live / 128) pages per segment, the entries of every segment are the oracle's
+    # (the checks of every step run after the call), and the loop goes on from the packed pages
+    w = ki.workload("tiny", prefill=1500)
+    full = [1500 * w.n_layers * w.n_kv_heads + 64]
+    third = [full[0] // 3]
+    results = run_paged_both(w, [full, third, third, third, [third[0] // 2], [third[0] // 2]], device=DEV,
+                             defrag_at=(1, 2, 4))
+    check(results)
+    check_defrag(results, (1, 4))
+    assert results[2]["defrag"]["pages_before"] - results[2]["defrag"]["pages_after"] <= w.nseg   # little to do one step later
+
+
+def test_defragmentation_in_several_passes_with_empty_and_tight_segments():
+    # segments of up to 9000 entries shrink to a quarter: more than 1024 entries move in one segment (two passes
+    # of the move list); one segment is empty, one ends exactly on a page boundary; lookahead tail constants travel too
+    w = wl(1, 2, 2, 2, 128)
+    seg_len = np.array([9000, 0, 5 * P, 4100])
+    c, now = ki.ragged_cache(w, seg_len, reserve=1, salt=11)
+    n = int(seg_len.sum())
+    results = run_paged_both(w, [[n + 8], [n // 4], [n // 4], [8], [0]], device=DEV, cache_dict=c, now0=now.numpy(), horizon=2,
+                             defrag_at=(1, 3, 4))
+    check(results)
+    check_defrag(results, (1,), must_free=True)
+    check_defrag(results, (3, 4), must_free=False)                # a handful of entries, then none: nothing to pack
+    assert results[1]["defrag"]["pages_before"] - results[1]["defrag"]["pages_after"] > 2 * 1024 // P
+
+
+def test_defragmentation_of_a_tight_pool_changes_nothing():
+    w = ki.workload("tiny")
+    results = run_paged_both(w, [w.budget] * 3, device=DEV, defrag_at=(0,))
+    check(results)
+    d = results[0]["defrag"]                                      # right after the build every segment is packed
+    assert d["tight"] and d["pages_before"] == d["pages_after"] and d["free_gain"] == 0
