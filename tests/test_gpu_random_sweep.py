@@ -54,8 +54,12 @@ def test_random_configuration(seed):
         for i, r in enumerate(res):
             assert r["status"] == 0 and r["score_equal"] and r["keep_equal"] and r["cache_equal"], (seed, fused, i, r)
             assert r["attn_err"] <= ATTN_TOL and r["lse_err"] <= 2e-3 and r["lse_inf_equal"], (seed, fused, i, r)
-    res = run_paged_both(w, budgets, device=DEV, cache_dict=clone(), now0=now.numpy())
+    # every other seed also packs the pages after each eviction from the second step on
+    defrag_at = tuple(range(1, len(budgets))) if seed % 2 else ()
+    res = run_paged_both(w, budgets, device=DEV, cache_dict=clone(), now0=now.numpy(), defrag_at=defrag_at)
     for r in res:
+        if "defrag" in r:
+            assert r["defrag"]["tight"] and r["defrag"]["live_unchanged"], (seed, r)
         assert r["status"] == 0 and r.get("status_select", 0) == 0, (seed, r)
         assert r["structure"] == [] and r.get("structure_pre", []) == [], (seed, r)
         assert r["score_equal"] and r["keep_equal"] and r["kept_equal"] and r["cache_equal"], (seed, r)
