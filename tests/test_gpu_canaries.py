@@ -116,3 +116,28 @@ def test_nothing_is_written_outside_the_callers_buffers(mode, G, D):
         assert kv.kvtrim_poll_error(ctx) == 0, (mode, step)
         assert gd.intact(), (mode, step)
     assert torch.isfinite(out).all()
+
+
+@pytest.mark.parametrize("L,H,d_model,d_g,d_p,n_tok", [
+    (2, 2, 256, 64, 8, 5),            # per-token kernels: u in the scratch buffer
+    (2, 2, 256, 192, 8, 300),         # LDS-tiled first layer + readout
+    (3, 3, 1024, 512, 16, 257),       # folded path, W1 straight from its rows (the scratch cannot hold the copy)
+    (9, 2, 256, 256, 8, 260),         # folded path with the tiled copy of W1 in the scratch buffer
+    (2, 8, 256, 384, 8, 513),         # ... eight heads, token tail of one
+])
+def test_gate_forward_stays_inside_scratch_and_outputs(L, H, d_model, d_g, d_p, n_tok):
+    wts = ki.gate_weights(L, H, d_model, d_g, d_p, seed=3)
+    gate = kv.Gate.from_dict(wts, DEV)
+    ctx = kv.Context(1, L, H, H, 64, 1024)
+    gd = Guarded()
+    x = gd.make((L, n_tok, d_model), torch.bfloat16)
+    x.copy_(ki.gate_inputs(L, n_tok, d_model, salt=1))
+    scratch = gd.make((kv.kvtrim_gate_scratch_bytes(gate, n_tok, L) // 4,), torch.float32)
+    lb = gd.make((n_tok, L, H), torch.float32)
+    lt = gd.make((n_tok, L, H), torch.float32)
+    for _ in range(2):
+        kv.kvtrim_gate_forward(ctx, gate, x, n_tok, 0, L, 2, scratch, lb, lt)
+    assert kv.kvtrim_poll_error(ctx) == 0
+    torch.cuda.synchronize()
+    assert gd.intact()
+    assert bool(torch.isfinite(lb).all()) and bool((lb < 0).all()) and bool(torch.isfinite(lt).all())
