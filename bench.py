@@ -68,13 +68,24 @@ def bench_gate(args):
     scratch = torch.empty(kv.kvtrim_gate_scratch_bytes(gate, n_tok, L) // 4, dtype=torch.float32, device=dev)
     lb = torch.zeros(n_tok, L, H, dtype=torch.float32, device=dev)
     lt = torch.zeros(n_tok, L, H, dtype=torch.float32, device=dev) if horizon != 1 else None
+    prepared = None
+    if args.prepared:
+        prepared = torch.empty(kv.kvtrim_gate_prepared_bytes(gate, L, H) // 4, dtype=torch.float32, device=dev)
+        kv.kvtrim_gate_prepare(ctx, gate, prepared)
+
+    def forward(x):
+        if prepared is None:
+            kv.kvtrim_gate_forward(ctx, gate, x, n_tok, 0, L, horizon, scratch, lb, lt)
+        else:
+            kv.kvtrim_gate_forward_prepared(ctx, gate, prepared, x, n_tok, 0, L, horizon, scratch, lb, lt)
+
     for i in range(W):
-        kv.kvtrim_gate_forward(ctx, gate, xs[i % 4], n_tok, 0, L, horizon, scratch, lb, lt)
+        forward(xs[i % 4])
     torch.cuda.synchronize()
-    kv.kvtrim_profile_begin(ctx, 0x1F << 23)                     # k_gate_hidden, _readout, _fold, _prefill, _retile
+    kv.kvtrim_profile_begin(ctx, (0x1F << 23) | (1 << 29))       # k_gate_hidden, _readout, _fold, _prefill, _retile, _dot
     t0 = time.perf_counter()
     for i in range(K):
-        kv.kvtrim_gate_forward(ctx, gate, xs[i % 4], n_tok, 0, L, horizon, scratch, lb, lt)
+        forward(xs[i % 4])
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     prof = kv.kvtrim_profile_end(ctx)
@@ -88,7 +99,7 @@ def bench_gate(args):
         # the activation and the readout run in one kernel (the dominant one, a dense contraction)
         first, second = "k_gate_prefill", "k_gate_fold"
         h_ms = prof[first][0] / prof[first][1]
-        r_ms = prof[second][0] / prof[second][1]
+        r_ms = prof[second][0] / prof[second][1] if second in prof else None    # prepared: no fold inside the call
         roof = {"bound": "mfma", "kernel": first, "achieved": flops_hidden / (h_ms * 1e-3) / 1e12,
                 "peak": 2500.0, "unit": "TFLOP/s", "traffic": None, "flops_per_launch": flops_hidden}
         second_bytes = w2_bytes + L * H * (dg + 1) * 4
@@ -97,7 +108,7 @@ def bench_gate(args):
             roof["third_kernel"] = {"kernel": "k_gate_retile", "avg_launch_ms": t_ms,
                                     "achieved": 2 * w1_bytes / (t_ms * 1e-3) / 1e9, "unit": "GB/s"}
     else:
-        first, second = "k_gate_hidden", "k_gate_readout"
+        first, second = "k_gate_hidden", "k_gate_dot" if "k_gate_dot" in prof else "k_gate_readout"
         h_ms = prof[first][0] / prof[first][1]
         r_ms = prof[second][0] / prof[second][1]
         # first layer: W1 once per 64 tokens of a call, x once per 16-row tile group (cached), u written once
@@ -109,22 +120,23 @@ def bench_gate(args):
         else:
             roof = {"bound": "mfma", "kernel": first, "achieved": flops_hidden / (h_ms * 1e-3) / 1e12,
                     "peak": 2500.0, "unit": "TFLOP/s", "traffic": None, "flops_per_launch": flops_hidden}
-        second_bytes = w2_bytes + L * n_tok * dg * 4
+        second_bytes = (L * H * (dg + 1) * 4 if second == "k_gate_dot" else w2_bytes) + L * n_tok * dg * 4
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["avg_launch_ms"] = h_ms
     third = roof.pop("third_kernel", None)
-    roof["second_kernel"] = {"kernel": second, "avg_launch_ms": r_ms,
-                             "achieved": second_bytes / (r_ms * 1e-3) / 1e9, "unit": "GB/s"}
+    roof["second_kernel"] = None if r_ms is None else {"kernel": second, "avg_launch_ms": r_ms,
+                                                       "achieved": second_bytes / (r_ms * 1e-3) / 1e9, "unit": "GB/s"}
     if third:
         roof["third_kernel"] = third
-    log(f"[bench] gate forward, {n_tok} token(s): {ms:.4f} ms/call; {first} {h_ms * 1e3:.1f} us, "
-        f"{second} {r_ms * 1e3:.1f} us" + (f", k_gate_retile {third['avg_launch_ms'] * 1e3:.1f} us" if third else "") +
+    log(f"[bench] gate forward{' (prepared)' if prepared is not None else ''}, {n_tok} token(s): {ms:.4f} ms/call; "
+        f"{first} {h_ms * 1e3:.1f} us" + (f", {second} {r_ms * 1e3:.1f} us" if r_ms is not None else "") + (f", k_gate_retile {third['avg_launch_ms'] * 1e3:.1f} us" if third else "") +
         f"; {roof['achieved']:.0f} {roof['unit']}")
     result = {
         "metric": "retention-gate forward (32Lx8H, d_model 4096, d_g 512, d_p 128), tokens/s", "value": n_tok * 1e3 / ms,
         "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"gate forward for {n_tok} token(s) per call into all {L * H} (layer, KV head) lists; "
+        "config": {"prepared_weights": prepared is not None,
+                   "workload": f"gate forward for {n_tok} token(s) per call into all {L * H} (layer, KV head) lists; "
                                f"random weights, lookahead horizon {horizon if horizon > 0 else 'infinite'}"},
         "roofline": roof,
     }
@@ -264,6 +276,9 @@ def main():
     ap.add_argument("--gate", type=int, default=0, metavar="N_TOK",
                     help="time the retention-gate forward alone (the metric model's shape: 32 layers x 8 KV heads, "
                          "d_model 4096, hidden width 512, projection width 128) for N_TOK tokens per call")
+    ap.add_argument("--prepared", action="store_true",
+                    help="with --gate: fold the readout and re-tile W1 once before the timed calls (kvtrim_gate_prepare) "
+                         "and time kvtrim_gate_forward_prepared - weights that do not change between calls")
     ap.add_argument("--chunk", type=int, default=0, metavar="N_TOK",
                     help="time the chunked-prefill step of the multi-turn workload instead of decode steps: N_TOK new "
                          "tokens per segment, then rescore, select, compact (the paper-shaped chunk is 4096)")

@@ -330,6 +330,23 @@ kvtrim_status kvtrim_gate_forward(kvtrim_ctx *ctx, const kvtrim_gate *g, const v
                                   int32_t layer_begin, int32_t layer_end, int32_t horizon, void *scratch,
                                   float *log_beta_out, float *log_tail_out, void *hip_stream);
 
+/* Weights that stay the same from call to call (inference): what kvtrim_gate_forward derives from them inside
+ * every call - the folded readout vectors v = W2^T w_g and constants s = w_g . c2 + b_g of every (layer, head),
+ * and a copy of W1 in matrix-core operand order - can be computed once and handed to
+ * kvtrim_gate_forward_prepared.  kvtrim_gate_prepared_bytes: size of that buffer for a context with n_layers
+ * layers and n_kv_heads heads (host-only; 0 for invalid arguments).  kvtrim_gate_prepare: fills `prepared`
+ * (device memory, 16-byte aligned, that many bytes, caller-owned) for ALL layers of the context; two kernels on
+ * the stream.  The buffer is valid for as long as the weights it was made from are unchanged.
+ * kvtrim_gate_forward_prepared: same arguments, outputs and arithmetic contract as kvtrim_gate_forward (g must
+ * be the gate the buffer was prepared from; scratch as for kvtrim_gate_forward); calls of every length then read
+ * the readout as one dot product per (token, layer, head), and the one-kernel path that kvtrim_gate_forward
+ * takes from 128 tokens on is taken from 24 tokens on, reading W1 from the operand-order copy. */
+size_t kvtrim_gate_prepared_bytes(const kvtrim_gate *g, int32_t n_layers, int32_t n_kv_heads);
+kvtrim_status kvtrim_gate_prepare(kvtrim_ctx *ctx, const kvtrim_gate *g, void *prepared, void *hip_stream);
+kvtrim_status kvtrim_gate_forward_prepared(kvtrim_ctx *ctx, const kvtrim_gate *g, const void *prepared, const void *x,
+                                           int32_t n_tok, int32_t layer_begin, int32_t layer_end, int32_t horizon,
+                                           void *scratch, float *log_beta_out, float *log_tail_out, void *hip_stream);
+
 /* Instrumentation (for the benchmark; not a step of the method).  Between
  * kvtrim_profile_begin and kvtrim_profile_end every launch of a kernel whose bit is
  * set in `kernel_mask` (bit i = kernel id i, names from kvtrim_kernel_name) is
@@ -339,7 +356,7 @@ kvtrim_status kvtrim_gate_forward(kvtrim_ctx *ctx, const kvtrim_gate *g, const v
  * end waits for `hip_stream` and writes, per kernel id, the summed duration in
  * milliseconds and the number of bracketed launches into host arrays of
  * KVTRIM_N_KERNELS elements.  Do not capture a HIP graph while profiling is on. */
-#define KVTRIM_N_KERNELS 29
+#define KVTRIM_N_KERNELS 30
 #define KVTRIM_PROFILE_MAX_LAUNCHES 4096
 kvtrim_status kvtrim_profile_begin(kvtrim_ctx *ctx, uint32_t kernel_mask);
 kvtrim_status kvtrim_profile_end(kvtrim_ctx *ctx, void *hip_stream, double *ms_sum_host,

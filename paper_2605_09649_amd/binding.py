@@ -15,11 +15,12 @@ EXPORTS = ["kvtrim_create", "kvtrim_destroy", "kvtrim_workspace_bytes", "kvtrim_
            "kvtrim_poll_error", "kvtrim_score", "kvtrim_select_global", "kvtrim_compact",
            "kvtrim_decode_attn", "kvtrim_decode_attn_soft", "kvtrim_occupancy", "kvtrim_compact_attn", "kvtrim_append",
            "kvtrim_paged_build", "kvtrim_paged_append", "kvtrim_paged_score", "kvtrim_paged_select",
-           "kvtrim_paged_evict", "kvtrim_paged_defrag", "kvtrim_paged_attn", "kvtrim_gate_scratch_bytes", "kvtrim_gate_forward",
+           "kvtrim_paged_evict", "kvtrim_paged_defrag", "kvtrim_paged_attn", "kvtrim_gate_scratch_bytes", "kvtrim_gate_forward", "kvtrim_gate_prepared_bytes", "kvtrim_gate_prepare",
+           "kvtrim_gate_forward_prepared",
            "kvtrim_profile_begin", "kvtrim_profile_end",
            "kvtrim_kernel_name"]
 PAGE_SIZE = 128
-N_KERNELS = 29
+N_KERNELS = 30
 
 
 class KvtrimError(RuntimeError):
@@ -100,13 +101,18 @@ def load_library():
         lib.kvtrim_gate_scratch_bytes.restype = C.c_size_t
         lib.kvtrim_gate_forward.argtypes = [C.c_void_p, C.POINTER(_Gate), C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                             C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.kvtrim_gate_prepared_bytes.argtypes = [C.POINTER(_Gate), C.c_int32, C.c_int32]
+        lib.kvtrim_gate_prepared_bytes.restype = C.c_size_t
+        lib.kvtrim_gate_prepare.argtypes = [C.c_void_p, C.POINTER(_Gate), C.c_void_p, C.c_void_p]
+        lib.kvtrim_gate_forward_prepared.argtypes = [C.c_void_p, C.POINTER(_Gate), C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                                     C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.kvtrim_profile_begin.argtypes = [C.c_void_p, C.c_uint32]
         lib.kvtrim_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         lib.kvtrim_kernel_name.argtypes = [C.c_int32]
         lib.kvtrim_kernel_name.restype = C.c_char_p
         for name in EXPORTS:
             if name not in ("kvtrim_workspace_bytes", "kvtrim_last_error", "kvtrim_kernel_name",
-                            "kvtrim_gate_scratch_bytes"):
+                            "kvtrim_gate_scratch_bytes", "kvtrim_gate_prepared_bytes"):
                 getattr(lib, name).restype = C.c_int
         _lib = lib
     return _lib
@@ -358,6 +364,23 @@ def kvtrim_gate_forward(ctx, gate, x, n_tok, layer_begin, layer_end, horizon, sc
         ctx.handle, C.byref(gate.c), _ptr(x, torch.bfloat16), int(n_tok), int(layer_begin), int(layer_end), int(horizon),
         _ptr(scratch), _ptr(log_beta_out, torch.float32), _ptr(log_tail_out, torch.float32), _stream(stream)),
         "kvtrim_gate_forward")
+
+
+def kvtrim_gate_prepared_bytes(gate, n_layers, n_kv_heads):
+    return int(load_library().kvtrim_gate_prepared_bytes(C.byref(gate.c), int(n_layers), int(n_kv_heads)))
+
+
+def kvtrim_gate_prepare(ctx, gate, prepared, stream=None):
+    _check(ctx, load_library().kvtrim_gate_prepare(ctx.handle, C.byref(gate.c), _ptr(prepared), _stream(stream)),
+           "kvtrim_gate_prepare")
+
+
+def kvtrim_gate_forward_prepared(ctx, gate, prepared, x, n_tok, layer_begin, layer_end, horizon, scratch, log_beta_out,
+                                 log_tail_out=None, stream=None):
+    _check(ctx, load_library().kvtrim_gate_forward_prepared(
+        ctx.handle, C.byref(gate.c), _ptr(prepared), _ptr(x, torch.bfloat16), int(n_tok), int(layer_begin), int(layer_end),
+        int(horizon), _ptr(scratch), _ptr(log_beta_out, torch.float32), _ptr(log_tail_out, torch.float32), _stream(stream)),
+        "kvtrim_gate_forward_prepared")
 
 
 def kvtrim_kernel_name(kernel_id):

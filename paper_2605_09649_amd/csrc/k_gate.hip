@@ -636,33 +636,106 @@ __global__ __launch_bounds__(GP_THREADS) void k_gate_prefill(GateView g, const u
 #define KVTRIM_GATE_PREFILL_MIN_TOK 128
 #endif
 constexpr int GP_MIN_TOK = KVTRIM_GATE_PREFILL_MIN_TOK;
+constexpr int GP_MIN_TOK_PREPARED = 24;
 
 static bool prefill_shape(const kvtrim_ctx* ctx, const GateView& g) {
     return g.d_g % 128 == 0 && g.d_g <= 512 && ctx->shape.n_kv_heads <= GP_HEADS_MAX;
 }
 
-kvtrim_status launch_gate(kvtrim_ctx* ctx, const GateView& g, const uint16_t* x, int n_tok, int layer_begin, int layer_end,
-                          int horizon, float* scratch, float* log_beta_out, float* log_tail_out, hipStream_t st) {
+// Readout from folded vectors for calls that went through the per-token first-layer kernels: one wavefront
+// per (token, layer, head) forms z = v . u + s - every dot product is one trip to memory, all of them at once.
+constexpr int GD_THREADS = 256;
+
+__global__ __launch_bounds__(GD_THREADS) void k_gate_dot(const float* __restrict__ u, const float* __restrict__ v,
+                                                         const float* __restrict__ sconst, int n_tok, int d_g,
+                                                         int layer_begin, int n_layers, int n_heads, int horizon,
+                                                         float* __restrict__ log_beta_out,
+                                                         float* __restrict__ log_tail_out) {
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int64_t item = (int64_t)blockIdx.x * (GD_THREADS / 64) + wave;    // (token, head) of layer blockIdx.y
+    const int lr = blockIdx.y;
+    if (item >= (int64_t)n_tok * n_heads) return;
+    const int tok = (int)(item / n_heads), h = (int)(item % n_heads);
+    const float* urow = u + ((size_t)lr * n_tok + tok) * d_g;
+    const float* vh = v + ((size_t)lr * n_heads + h) * d_g;
+    float acc = 0.f;
+    for (int k = lane; k < d_g; k += 64) acc = fmaf(urow[k], vh[k], acc);
+    acc = wave_sum(acc);
+    if (lane == 0) {
+        const float lb = log_sigmoid(acc + sconst[(size_t)lr * n_heads + h]);
+        const size_t o = ((size_t)tok * n_layers + layer_begin + lr) * n_heads + h;
+        log_beta_out[o] = lb;
+        if (log_tail_out) log_tail_out[o] = log_tail_of(lb, horizon);
+    }
+}
+
+// Layout of a prepared buffer (kvtrim_gate_prepare): v [L][heads][d_g], s [L][heads], padding to 16 bytes, then
+// W1 of all L layers in operand-order tiles.
+static size_t prepared_fold_floats(const GateView& g, int n_layers, int n_heads) {
+    return ((size_t)n_layers * n_heads * (g.d_g + 1) + 3) & ~(size_t)3;
+}
+
+kvtrim_status launch_gate_prepare(kvtrim_ctx* ctx, const GateView& g, float* prepared, hipStream_t st) {
+    const int L = ctx->shape.n_layers, n_heads = ctx->shape.n_kv_heads;
+    float* v = prepared;
+    float* sconst = prepared + (size_t)L * n_heads * g.d_g;
+    uint4* tiled = reinterpret_cast<uint4*>(prepared + prepared_fold_floats(g, L, n_heads));
+    {
+        ProfScope prof(ctx, K_GATE_FOLD, st);
+        hipLaunchKernelGGL(k_gate_fold, dim3(n_heads, L), dim3(GF_THREADS), 0, st, g, 0, n_heads, v, sconst);
+    }
+    {
+        ProfScope prof(ctx, K_GATE_RETILE, st);
+        const int steps = g.d_model >> 6;
+        hipLaunchKernelGGL(k_gate_retile, dim3((steps / 4 + GT_THREADS / 64 - 1) / (GT_THREADS / 64), g.d_g / 16, L),
+                           dim3(GT_THREADS), 0, st, g, 0, tiled);
+    }
+    KVTRIM_HIP(ctx, hipGetLastError());
+    return KVTRIM_OK;
+}
+
+// prepared: NULL (everything is derived from the weights inside the call) or a buffer filled by launch_gate_prepare
+// for the same weights.
+kvtrim_status launch_gate(kvtrim_ctx* ctx, const GateView& g, const float* prepared, const uint16_t* x, int n_tok,
+                          int layer_begin, int layer_end, int horizon, float* scratch, float* log_beta_out,
+                          float* log_tail_out, hipStream_t st) {
     const int nl = layer_end - layer_begin;
-    const int n_heads = ctx->shape.n_kv_heads;
-    if (n_tok >= GP_MIN_TOK && prefill_shape(ctx, g)) {
-        // scratch: v [nl][heads][d_g], s [nl][heads], then (16-byte aligned) the tiled copy of W1 if the buffer
-        // - n_tok * nl * d_g floats - has room for it, which also means the call is long enough for the pass to pay
-        float* v = scratch;
-        float* sconst = scratch + (size_t)nl * n_heads * g.d_g;
-        const size_t fold_floats = ((size_t)nl * n_heads * (g.d_g + 1) + 3) & ~(size_t)3;
-        const size_t tiled_floats = (size_t)nl * g.d_g * g.d_model / 2;
-        const bool use_tiled = fold_floats + tiled_floats <= (size_t)n_tok * nl * g.d_g;
-        uint4* tiled = reinterpret_cast<uint4*>(scratch + fold_floats);
-        {
-            ProfScope prof(ctx, K_GATE_FOLD, st);
-            hipLaunchKernelGGL(k_gate_fold, dim3(n_heads, nl), dim3(GF_THREADS), 0, st, g, layer_begin, n_heads, v, sconst);
-        }
-        if (use_tiled) {
-            ProfScope prof(ctx, K_GATE_RETILE, st);
-            const int steps = g.d_model >> 6;
-            hipLaunchKernelGGL(k_gate_retile, dim3((steps / 4 + GT_THREADS / 64 - 1) / (GT_THREADS / 64), g.d_g / 16, nl),
-                               dim3(GT_THREADS), 0, st, g, layer_begin, tiled);
+    const int L = ctx->shape.n_layers, n_heads = ctx->shape.n_kv_heads;
+    // the folded vectors and the tiled W1 of the layer range, when prepared
+    const float* pv = prepared ? prepared + (size_t)layer_begin * n_heads * g.d_g : nullptr;
+    const float* ps = prepared ? prepared + (size_t)L * n_heads * g.d_g + (size_t)layer_begin * n_heads : nullptr;
+    const uint4* ptiled = prepared ? reinterpret_cast<const uint4*>(prepared + prepared_fold_floats(g, L, n_heads)) +
+                                         (size_t)layer_begin * (g.d_g >> 4) * (g.d_model >> 6) * 128
+                                   : nullptr;
+    // with prepared weights the folded kernel has no per-call passes to pay for and wins from 24 tokens on
+    // (measured: 16 tokens 54 us per-token kernels / 58 us folded, 32 tokens 70 / 59, 64 tokens 104 / 58)
+    if (n_tok >= (prepared ? GP_MIN_TOK_PREPARED : GP_MIN_TOK) && prefill_shape(ctx, g)) {
+        const float* v = pv;
+        const float* sconst = ps;
+        const uint4* tiled = ptiled;
+        bool use_tiled = prepared != nullptr;
+        if (!prepared) {
+            // scratch: v [nl][heads][d_g], s [nl][heads], then (16-byte aligned) the tiled copy of W1 if the buffer
+            // - n_tok * nl * d_g floats - has room for it, which also means the call is long enough for the pass to pay
+            float* sv = scratch;
+            float* ss = scratch + (size_t)nl * n_heads * g.d_g;
+            const size_t fold_floats = ((size_t)nl * n_heads * (g.d_g + 1) + 3) & ~(size_t)3;
+            const size_t tiled_floats = (size_t)nl * g.d_g * g.d_model / 2;
+            use_tiled = fold_floats + tiled_floats <= (size_t)n_tok * nl * g.d_g;
+            uint4* st_tiled = reinterpret_cast<uint4*>(scratch + fold_floats);
+            {
+                ProfScope prof(ctx, K_GATE_FOLD, st);
+                hipLaunchKernelGGL(k_gate_fold, dim3(n_heads, nl), dim3(GF_THREADS), 0, st, g, layer_begin, n_heads, sv, ss);
+            }
+            if (use_tiled) {
+                ProfScope prof(ctx, K_GATE_RETILE, st);
+                const int steps = g.d_model >> 6;
+                hipLaunchKernelGGL(k_gate_retile, dim3((steps / 4 + GT_THREADS / 64 - 1) / (GT_THREADS / 64), g.d_g / 16, nl),
+                                   dim3(GT_THREADS), 0, st, g, layer_begin, st_tiled);
+            }
+            v = sv;
+            sconst = ss;
+            tiled = st_tiled;
         }
         {
             ProfScope prof(ctx, K_GATE_PREFILL, st);
@@ -672,11 +745,13 @@ kvtrim_status launch_gate(kvtrim_ctx* ctx, const GateView& g, const uint16_t* x,
             const int tiles = (n_tok + 16 * tt - 1) / (16 * tt);
             const dim3 grid(8u * (unsigned)((nl + 7) / 8) * (unsigned)tiles);
 #define KVTRIM_GATE_PREFILL(HT, TT, TILED)                                                                                    \
-    hipLaunchKernelGGL((k_gate_prefill<HT, TT, TILED>), grid, dim3(GP_THREADS), 0, st, g, x, n_tok, layer_begin, nl,          \
-                       ctx->shape.n_layers, n_heads, horizon, tiled, v, sconst, log_beta_out, log_tail_out)
+    hipLaunchKernelGGL((k_gate_prefill<HT, TT, TILED>), grid, dim3(GP_THREADS), 0, st, g, x, n_tok, layer_begin, nl, L,       \
+                       n_heads, horizon, tiled, v, sconst, log_beta_out, log_tail_out)
 #define KVTRIM_GATE_PREFILL_TT(HT)                                                                                            \
     do {                                                                                                                      \
-        if (use_tiled) KVTRIM_GATE_PREFILL(HT, 8, true);       /* room for the tiled copy implies 128-token blocks */         \
+        if (use_tiled && tt == 8) KVTRIM_GATE_PREFILL(HT, 8, true);                                                           \
+        else if (use_tiled && tt == 4) KVTRIM_GATE_PREFILL(HT, 4, true);                                                      \
+        else if (use_tiled) KVTRIM_GATE_PREFILL(HT, 2, true);                                                                 \
         else if (tt == 8) KVTRIM_GATE_PREFILL(HT, 8, false);                                                                  \
         else if (tt == 4) KVTRIM_GATE_PREFILL(HT, 4, false);                                                                  \
         else KVTRIM_GATE_PREFILL(HT, 2, false);                                                                               \
@@ -707,10 +782,15 @@ kvtrim_status launch_gate(kvtrim_ctx* ctx, const GateView& g, const uint16_t* x,
             hipLaunchKernelGGL(k_gate_hidden_gemm, dim3((g.d_g + GG_BM - 1) / GG_BM, (n_tok + GG_BN - 1) / GG_BN, nl), dim3(256), 0,
                                st, g, x, n_tok, layer_begin, scratch);
     }
-    {
+    if (prepared) {
+        ProfScope prof(ctx, K_GATE_DOT, st);
+        const int64_t items = (int64_t)n_tok * n_heads;
+        hipLaunchKernelGGL(k_gate_dot, dim3((unsigned)((items + GD_THREADS / 64 - 1) / (GD_THREADS / 64)), nl), dim3(GD_THREADS), 0,
+                           st, scratch, pv, ps, n_tok, g.d_g, layer_begin, L, n_heads, horizon, log_beta_out, log_tail_out);
+    } else {
         ProfScope prof(ctx, K_GATE_READOUT, st);
         hipLaunchKernelGGL(k_gate_readout, dim3(n_heads, nl, (n_tok + 15) / 16), dim3(GR_THREADS), 0, st, g, scratch,
-                           n_tok, layer_begin, ctx->shape.n_layers, n_heads, horizon, log_beta_out, log_tail_out);
+                           n_tok, layer_begin, L, n_heads, horizon, log_beta_out, log_tail_out);
     }
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;
@@ -729,27 +809,19 @@ size_t kvtrim_gate_scratch_bytes(const kvtrim_gate* g, int32_t n_tok, int32_t n_
     return (size_t)n_tok * (size_t)n_layers * (size_t)g->d_g * sizeof(float);
 }
 
-kvtrim_status kvtrim_gate_forward(kvtrim_ctx* ctx, const kvtrim_gate* g, const void* x, int32_t n_tok, int32_t layer_begin,
-                                  int32_t layer_end, int32_t horizon, void* scratch, float* log_beta_out,
-                                  float* log_tail_out, void* hip_stream) {
-    if (!ctx) return KVTRIM_EINVAL;
-    auto bad = [&](const char* why) {
-        snprintf(ctx->last_error, sizeof(ctx->last_error), "invalid argument: %s", why);
-        return KVTRIM_EINVAL;
-    };
-    if (!g || !g->w1 || !g->c1 || !g->w2 || !g->c2 || !g->w_g) return bad("gate or one of its weight pointers is NULL");
-    if (!x || !scratch || !log_beta_out) return bad("x / scratch / log_beta_out is NULL");
-    if (g->d_model < 256 || g->d_model % 256) return bad("d_model must be a positive multiple of 256");
-    if (g->d_g < 64 || g->d_g % 64) return bad("d_g must be a positive multiple of 64");
-    if (g->d_p < 1) return bad("d_p < 1");
-    if (n_tok < 1) return bad("n_tok < 1");
-    if ((int64_t)n_tok > 65535 * 16) return bad("n_tok too large for one call");
-    if ((((uintptr_t)g->c1) | ((uintptr_t)g->w_g)) & 15) return bad("c1 / w_g not 16-byte aligned");
-    if (layer_begin < 0 || layer_end > ctx->cfg.n_layers || layer_begin >= layer_end) return bad("empty or out-of-range layer range");
-    if (horizon < 0 || horizon > 4096) return bad("horizon outside [0, 4096] (0 = infinite)");
-    if ((((uintptr_t)x) | ((uintptr_t)g->w1) | ((uintptr_t)g->w2) | ((uintptr_t)scratch)) & 15)
-        return bad("x / w1 / w2 / scratch not 16-byte aligned");
-    if (!(g->b_g == g->b_g)) return bad("b_g is NaN");
+// argument checks shared by the gate entry points; returns NULL when the gate itself is usable
+static const char* gate_problem(const kvtrim_gate* g) {
+    if (!g || !g->w1 || !g->c1 || !g->w2 || !g->c2 || !g->w_g) return "gate or one of its weight pointers is NULL";
+    if (g->d_model < 256 || g->d_model % 256) return "d_model must be a positive multiple of 256";
+    if (g->d_g < 64 || g->d_g % 64) return "d_g must be a positive multiple of 64";
+    if (g->d_p < 1) return "d_p < 1";
+    if ((((uintptr_t)g->c1) | ((uintptr_t)g->w_g)) & 15) return "c1 / w_g not 16-byte aligned";
+    if ((((uintptr_t)g->w1) | ((uintptr_t)g->w2)) & 15) return "w1 / w2 not 16-byte aligned";
+    if (!(g->b_g == g->b_g)) return "b_g is NaN";
+    return nullptr;
+}
+
+static GateView gate_view(const kvtrim_gate* g) {
     GateView v;
     v.w1 = (const uint16_t*)g->w1;
     v.c1 = g->c1;
@@ -760,8 +832,62 @@ kvtrim_status kvtrim_gate_forward(kvtrim_ctx* ctx, const kvtrim_gate* g, const v
     v.d_model = g->d_model;
     v.d_g = g->d_g;
     v.d_p = g->d_p;
-    return launch_gate(ctx, v, (const uint16_t*)x, n_tok, layer_begin, layer_end, horizon, (float*)scratch, log_beta_out,
-                       log_tail_out, (hipStream_t)hip_stream);
+    return v;
+}
+
+static kvtrim_status gate_forward(kvtrim_ctx* ctx, const kvtrim_gate* g, const void* prepared, const void* x, int32_t n_tok,
+                                  int32_t layer_begin, int32_t layer_end, int32_t horizon, void* scratch,
+                                  float* log_beta_out, float* log_tail_out, void* hip_stream) {
+    auto bad = [&](const char* why) {
+        snprintf(ctx->last_error, sizeof(ctx->last_error), "invalid argument: %s", why);
+        return KVTRIM_EINVAL;
+    };
+    if (const char* p = gate_problem(g)) return bad(p);
+    if (!x || !scratch || !log_beta_out) return bad("x / scratch / log_beta_out is NULL");
+    if (n_tok < 1) return bad("n_tok < 1");
+    if ((int64_t)n_tok > 65535 * 16) return bad("n_tok too large for one call");
+    if (layer_begin < 0 || layer_end > ctx->cfg.n_layers || layer_begin >= layer_end) return bad("empty or out-of-range layer range");
+    if (horizon < 0 || horizon > 4096) return bad("horizon outside [0, 4096] (0 = infinite)");
+    if ((((uintptr_t)x) | ((uintptr_t)scratch) | ((uintptr_t)prepared)) & 15) return bad("x / scratch / prepared not 16-byte aligned");
+    return launch_gate(ctx, gate_view(g), (const float*)prepared, (const uint16_t*)x, n_tok, layer_begin, layer_end, horizon,
+                       (float*)scratch, log_beta_out, log_tail_out, (hipStream_t)hip_stream);
+}
+
+kvtrim_status kvtrim_gate_forward(kvtrim_ctx* ctx, const kvtrim_gate* g, const void* x, int32_t n_tok, int32_t layer_begin,
+                                  int32_t layer_end, int32_t horizon, void* scratch, float* log_beta_out,
+                                  float* log_tail_out, void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    return gate_forward(ctx, g, nullptr, x, n_tok, layer_begin, layer_end, horizon, scratch, log_beta_out, log_tail_out,
+                        hip_stream);
+}
+
+size_t kvtrim_gate_prepared_bytes(const kvtrim_gate* g, int32_t n_layers, int32_t n_kv_heads) {
+    if (gate_problem(g) || n_layers < 1 || n_kv_heads < 1) return 0;
+    const size_t fold = ((size_t)n_layers * n_kv_heads * ((size_t)g->d_g + 1) + 3) & ~(size_t)3;
+    return fold * sizeof(float) + (size_t)n_layers * g->d_g * g->d_model * 2;
+}
+
+kvtrim_status kvtrim_gate_prepare(kvtrim_ctx* ctx, const kvtrim_gate* g, void* prepared, void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    auto bad = [&](const char* why) {
+        snprintf(ctx->last_error, sizeof(ctx->last_error), "invalid argument: %s", why);
+        return KVTRIM_EINVAL;
+    };
+    if (const char* p = gate_problem(g)) return bad(p);
+    if (!prepared || (((uintptr_t)prepared) & 15)) return bad("prepared is NULL or not 16-byte aligned");
+    return launch_gate_prepare(ctx, gate_view(g), (float*)prepared, (hipStream_t)hip_stream);
+}
+
+kvtrim_status kvtrim_gate_forward_prepared(kvtrim_ctx* ctx, const kvtrim_gate* g, const void* prepared, const void* x,
+                                           int32_t n_tok, int32_t layer_begin, int32_t layer_end, int32_t horizon,
+                                           void* scratch, float* log_beta_out, float* log_tail_out, void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    if (!prepared) {
+        snprintf(ctx->last_error, sizeof(ctx->last_error), "invalid argument: prepared is NULL");
+        return KVTRIM_EINVAL;
+    }
+    return gate_forward(ctx, g, prepared, x, n_tok, layer_begin, layer_end, horizon, scratch, log_beta_out, log_tail_out,
+                        hip_stream);
 }
 
 }  // extern "C"

@@ -114,7 +114,7 @@ namespace kvtrim {
 enum KernelId {
     K_SCORE = 0, K_SEL_PLAN, K_SEL_HIST0, K_SEL_HIST1, K_SEL_HIST2, K_SEL_COUNT, K_SEL_MASK,
     K_CMP_SCAN, K_CMP_COPY, K_ATT_PLAN, K_ATT_PARTIAL, K_ATT_COMBINE, K_APPEND, K_CMP_ATTN, K_OCCUPANCY,
-    K_PG_INIT, K_PG_APPEND, K_PG_SCORE, K_PG_PLAN, K_PG_COUNT, K_PG_EVICT, K_PG_TIDY, K_PG_ATT_PLAN, K_GATE_HIDDEN, K_GATE_READOUT, K_GATE_FOLD, K_GATE_PREFILL, K_GATE_RETILE, K_PG_DEFRAG, K_COUNT
+    K_PG_INIT, K_PG_APPEND, K_PG_SCORE, K_PG_PLAN, K_PG_COUNT, K_PG_EVICT, K_PG_TIDY, K_PG_ATT_PLAN, K_GATE_HIDDEN, K_GATE_READOUT, K_GATE_FOLD, K_GATE_PREFILL, K_GATE_RETILE, K_PG_DEFRAG, K_GATE_DOT, K_COUNT
 };
 static_assert(K_COUNT == KVTRIM_N_KERNELS, "kernel table out of step with the header");
 }  // namespace kvtrim

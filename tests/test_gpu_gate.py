@@ -147,6 +147,41 @@ def test_full_size_gate_prefill_chunk_on_sampled_tokens():
     assert err <= RTOL
 
 
+@pytest.mark.parametrize("L,H,d_model,d_g,d_p,n_toks", [
+    (3, 2, 256, 64, 7, (1, 5, 20, 150)),          # per-token first layer + dot-product readout; hidden width not for the folded kernel
+    (2, 3, 512, 128, 20, (16, 23, 24, 127, 300)),  # across the switch-over at 24 tokens: 32-token blocks read W1 from the prepared tiles
+    (32, 2, 1280, 128, 8, (520,)),                 # 64-token blocks from the prepared tiles
+    (2, 8, 256, 512, 16, (64, 513, 1100)),         # the paper's hidden width, eight heads, 128-token blocks
+    (2, 2, 256, 576, 8, (256,)),                   # hidden width above 512: LDS-tiled first layer + dot-product readout
+])
+def test_prepared_gate_matches_the_oracle_and_is_reusable(L, H, d_model, d_g, d_p, n_toks):
+    w = ki.gate_weights(L, H, d_model, d_g, d_p, b_g=3.5, seed=99 + d_p)
+    og = oracle.Gate(bf16_bits(w["w1"]), w["c1"].numpy(), bf16_bits(w["w2"]), w["c2"].numpy(), w["w_g"].numpy(), 3.5)
+    ctx = kv.Context(1, L, H, H, 64, 1024)
+    gate = kv.Gate.from_dict(w, DEV)
+    nbytes = kv.kvtrim_gate_prepared_bytes(gate, L, H)
+    assert nbytes >= L * d_g * d_model * 2 + L * H * (d_g + 1) * 4
+    prepared = torch.empty(nbytes // 4, dtype=torch.float32, device=DEV)
+    kv.kvtrim_gate_prepare(ctx, gate, prepared)                   # once; every call below reuses it
+    for n_tok in n_toks:
+        x = ki.gate_inputs(L, n_tok, d_model, salt=n_tok)
+        pick = None if n_tok * L * d_g * d_model < 3e9 else sorted({0, 1, 63, 64, n_tok // 2, n_tok - 1})
+        x_ref = x if pick is None else x[:, pick].contiguous()
+        for lo, hi in ((0, L), (L // 2, L)):
+            _, lb_ref, lt_ref = oracle.gate_forward(og, bf16_bits(x_ref[lo:hi].contiguous()), lo, hi, 2)
+            scratch = torch.empty(kv.kvtrim_gate_scratch_bytes(gate, n_tok, hi - lo) // 4, dtype=torch.float32, device=DEV)
+            lb = torch.full((n_tok, L, H), float("nan"), dtype=torch.float32, device=DEV)
+            lt = torch.full((n_tok, L, H), float("nan"), dtype=torch.float32, device=DEV)
+            kv.kvtrim_gate_forward_prepared(ctx, gate, prepared, x[lo:hi].contiguous().to(DEV), n_tok, lo, hi, 2, scratch, lb, lt)
+            assert kv.kvtrim_poll_error(ctx) == 0
+            lb_h, lt_h = lb.cpu().numpy(), lt.cpu().numpy()
+            assert np.isnan(lb_h[:, :lo, :]).all()                # layers outside the range stay untouched
+            if pick is not None:
+                lb_h, lt_h = lb_h[pick], lt_h[pick]
+            assert rel_err(lb_h[:, lo:hi], lb_ref[:, lo:hi]) <= RTOL, (n_tok, lo, hi)
+            assert np.max(np.abs(lt_h[:, lo:hi] - lt_ref[:, lo:hi])) <= 1e-3 * np.max(np.abs(lt_ref[:, lo:hi])) + 1e-6
+
+
 def test_host_side_argument_checks_of_the_gate():
     L, H = 2, 2
     w = ki.gate_weights(L, H, 256, 64, 8)
@@ -168,3 +203,14 @@ def test_host_side_argument_checks_of_the_gate():
         kv.kvtrim_gate_forward(ctx, kv.Gate.from_dict(w_bad, DEV), x, 2, 0, L, 1, scratch, lb)
     assert kv.kvtrim_gate_scratch_bytes(gate, 2, L) == 2 * L * 64 * 4
     assert kv.kvtrim_gate_scratch_bytes(gate, 0, L) == 0
+    assert kv.kvtrim_gate_prepared_bytes(gate, 0, H) == 0 and kv.kvtrim_gate_prepared_bytes(gate, L, H) > 0
+    with pytest.raises(kv.KvtrimError):
+        kv.kvtrim_gate_prepare(ctx, gate, None)                                    # no buffer
+    prepared = torch.empty(kv.kvtrim_gate_prepared_bytes(gate, L, H) // 4, dtype=torch.float32, device=DEV)
+    kv.kvtrim_gate_prepare(ctx, gate, prepared)
+    with pytest.raises(kv.KvtrimError):
+        kv.kvtrim_gate_forward_prepared(ctx, gate, None, x, 2, 0, L, 1, scratch, lb)   # no prepared buffer
+    with pytest.raises(kv.KvtrimError):
+        kv.kvtrim_gate_forward_prepared(ctx, gate, prepared, x, 2, 1, 1, 1, scratch, lb)   # empty layer range
+    kv.kvtrim_gate_forward_prepared(ctx, gate, prepared, x, 2, 0, L, 1, scratch, lb)
+    assert kv.kvtrim_poll_error(ctx) == 0
