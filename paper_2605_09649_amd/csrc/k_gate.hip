@@ -45,9 +45,12 @@ constexpr int GH_THREADS = 256;          // four wavefronts split d_model
 constexpr int GH_ROWS = 16;
 
 // x: bf16 [layers of the range][n_tok][d_model]; u: fp32 [layers of the range][n_tok][d_g]
-template <int NT>
+// TILED: W1 comes from the operand-order copy of a prepared buffer (`tiled` points at the first layer of the
+// range: [layer][16-row tile][64-wide step][half][lane] 16-byte pieces), so a wavefront load reads 1 KB in one piece.
+template <int NT, bool TILED>
 __global__ __launch_bounds__(GH_THREADS) void k_gate_hidden(GateView g, const uint16_t* __restrict__ x, int n_tok,
-                                                            int layer_begin, float* __restrict__ u) {
+                                                            int layer_begin, const uint4* __restrict__ tiled,
+                                                            float* __restrict__ u) {
     __shared__ float s_part[4][NT][16][17];
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int r16 = lane & 15, g4 = lane >> 4;
@@ -58,7 +61,10 @@ __global__ __launch_bounds__(GH_THREADS) void k_gate_hidden(GateView g, const ui
     const int kw = g.d_model >> 2;                                   // contraction share of a wavefront
     const int k_begin = wave * kw;
 
-    const uint4* arow = reinterpret_cast<const uint4*>(g.w1 + ((size_t)layer * g.d_g + row0 + r16) * g.d_model + k_begin + 16 * g4);
+    // piece p (0, 1) of step s sits at arow[s * a_step + p * a_half]
+    const uint4* arow = TILED ? tiled + (((size_t)lr * (g.d_g >> 4) + blockIdx.x) * (g.d_model >> 6) + (k_begin >> 6)) * 128 + lane
+                              : reinterpret_cast<const uint4*>(g.w1 + ((size_t)layer * g.d_g + row0 + r16) * g.d_model + k_begin + 16 * g4);
+    constexpr int a_step = TILED ? 128 : 8, a_half = TILED ? 64 : 1;
     const uint4* brow[NT];
     bool bval[NT];
 #pragma unroll
@@ -79,8 +85,8 @@ __global__ __launch_bounds__(GH_THREADS) void k_gate_hidden(GateView g, const ui
 #pragma unroll
         for (int i = 0; i < AHEAD; ++i) {
             if (s0 + i < steps) {
-                a[i][0] = arow[(s0 + i) * 8];
-                a[i][1] = arow[(s0 + i) * 8 + 1];
+                a[i][0] = arow[(s0 + i) * a_step];
+                a[i][1] = arow[(s0 + i) * a_step + a_half];
             } else {
                 a[i][0] = a[i][1] = make_uint4(0, 0, 0, 0);
             }
@@ -771,13 +777,21 @@ kvtrim_status launch_gate(kvtrim_ctx* ctx, const GateView& g, const float* prepa
     {
         ProfScope prof(ctx, K_GATE_HIDDEN, st);
         const dim3 grid1(g.d_g / GH_ROWS, nl, 1);
-        if (n_tok <= 16)
-            hipLaunchKernelGGL(k_gate_hidden<1>, dim3(grid1.x, nl, 1), dim3(GH_THREADS), 0, st, g, x, n_tok, layer_begin, scratch);
+        if (n_tok <= 16 && prepared)
+            hipLaunchKernelGGL((k_gate_hidden<1, true>), dim3(grid1.x, nl, 1), dim3(GH_THREADS), 0, st, g, x, n_tok, layer_begin,
+                               ptiled, scratch);
+        else if (n_tok <= 32 && prepared)
+            hipLaunchKernelGGL((k_gate_hidden<2, true>), dim3(grid1.x, nl, 1), dim3(GH_THREADS), 0, st, g, x, n_tok, layer_begin,
+                               ptiled, scratch);
+        else if (n_tok <= 16)
+            hipLaunchKernelGGL((k_gate_hidden<1, false>), dim3(grid1.x, nl, 1), dim3(GH_THREADS), 0, st, g, x, n_tok, layer_begin,
+                               ptiled, scratch);
         else if (n_tok <= 32)
-            hipLaunchKernelGGL(k_gate_hidden<2>, dim3(grid1.x, nl, 1), dim3(GH_THREADS), 0, st, g, x, n_tok, layer_begin, scratch);
+            hipLaunchKernelGGL((k_gate_hidden<2, false>), dim3(grid1.x, nl, 1), dim3(GH_THREADS), 0, st, g, x, n_tok, layer_begin,
+                               ptiled, scratch);
         else if (n_tok < 256)                                        // below that the tiled kernel cannot fill the chip
-            hipLaunchKernelGGL(k_gate_hidden<4>, dim3(grid1.x, nl, (n_tok + 63) / 64), dim3(GH_THREADS), 0, st, g, x, n_tok,
-                               layer_begin, scratch);
+            hipLaunchKernelGGL((k_gate_hidden<4, false>), dim3(grid1.x, nl, (n_tok + 63) / 64), dim3(GH_THREADS), 0, st, g, x, n_tok,
+                               layer_begin, ptiled, scratch);
         else
             hipLaunchKernelGGL(k_gate_hidden_gemm, dim3((g.d_g + GG_BM - 1) / GG_BM, (n_tok + GG_BN - 1) / GG_BN, nl), dim3(256), 0,
                                st, g, x, n_tok, layer_begin, scratch);
