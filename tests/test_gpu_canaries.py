@@ -120,6 +120,7 @@ def test_nothing_is_written_outside_the_callers_buffers(mode, G, D):
 
 @pytest.mark.parametrize("L,H,d_model,d_g,d_p,n_tok", [
     (2, 2, 256, 64, 8, 5),            # per-token kernels: u in the scratch buffer
+    (2, 2, 256, 128, 8, 40),          # ... 40 tokens: with prepared weights already the folded kernel
     (2, 2, 256, 192, 8, 300),         # LDS-tiled first layer + readout
     (3, 3, 1024, 512, 16, 257),       # folded path, W1 straight from its rows (the scratch cannot hold the copy)
     (9, 2, 256, 256, 8, 260),         # folded path with the tiled copy of W1 in the scratch buffer
@@ -141,3 +142,13 @@ def test_gate_forward_stays_inside_scratch_and_outputs(L, H, d_model, d_g, d_p, 
     torch.cuda.synchronize()
     assert gd.intact()
     assert bool(torch.isfinite(lb).all()) and bool((lb < 0).all()) and bool(torch.isfinite(lt).all())
+    # the same with the weight-only work done once into a guarded buffer
+    prepared = gd.make((kv.kvtrim_gate_prepared_bytes(gate, L, H) // 4,), torch.float32)
+    kv.kvtrim_gate_prepare(ctx, gate, prepared)
+    lb2 = gd.make((n_tok, L, H), torch.float32)
+    for _ in range(2):
+        kv.kvtrim_gate_forward_prepared(ctx, gate, prepared, x, n_tok, 0, L, 2, scratch, lb2, lt)
+    assert kv.kvtrim_poll_error(ctx) == 0
+    torch.cuda.synchronize()
+    assert gd.intact()
+    assert bool(((lb2 - lb).abs() <= 2e-4 * lb.abs()).all())
