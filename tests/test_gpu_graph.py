@@ -146,3 +146,45 @@ def test_two_captured_steps_replayed_three_times_match_the_eager_loop(paged):
         torch.cuda.synchronize()
         assert kv.kvtrim_poll_error(eager.ctx) == 0 and kv.kvtrim_poll_error(graphed.ctx) == 0
         assert same(eager.snapshot(), graphed.snapshot()), f"replay {r} differs from the eager steps {s0}, {s1}"
+
+
+@pytest.mark.parametrize("n_tok,prepared", [(1, False), (3, True), (40, True), (130, False)])
+def test_captured_gate_forward_matches_the_eager_call(n_tok, prepared):
+    # the gate forward is two or three kernel launches on the caller's stream: captured once, replayed with new
+    # token representations in the same buffers, it must give the eager call's bits
+    L, H, d_model, d_g, d_p = 3, 2, 512, 128, 16
+    wts = ki.gate_weights(L, H, d_model, d_g, d_p, seed=5)
+    gate = kv.Gate.from_dict(wts, DEV)
+    ctx = kv.Context(1, L, H, H, 64, 1024)
+    prep = None
+    if prepared:
+        prep = torch.empty(kv.kvtrim_gate_prepared_bytes(gate, L, H) // 4, dtype=torch.float32, device=DEV)
+        kv.kvtrim_gate_prepare(ctx, gate, prep)
+    x = torch.zeros(L, n_tok, d_model, dtype=torch.bfloat16, device=DEV)
+    scratch = torch.empty(kv.kvtrim_gate_scratch_bytes(gate, n_tok, L) // 4, dtype=torch.float32, device=DEV)
+    lb_g, lt_g = (torch.zeros(n_tok, L, H, dtype=torch.float32, device=DEV) for _ in range(2))
+    lb_e, lt_e = (torch.zeros(n_tok, L, H, dtype=torch.float32, device=DEV) for _ in range(2))
+
+    def call(lb, lt):
+        if prepared:
+            kv.kvtrim_gate_forward_prepared(ctx, gate, prep, x, n_tok, 0, L, 2, scratch, lb, lt)
+        else:
+            kv.kvtrim_gate_forward(ctx, gate, x, n_tok, 0, L, 2, scratch, lb, lt)
+
+    x.copy_(ki.gate_inputs(L, n_tok, d_model, salt=0))
+    call(lb_e, lt_e)                                              # warm-up outside the capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        call(lb_g, lt_g)
+    torch.cuda.synchronize()
+    for r in range(1, 4):
+        x.copy_(ki.gate_inputs(L, n_tok, d_model, salt=r))
+        g.replay()
+        torch.cuda.synchronize()
+        scratch.fill_(float("nan"))                               # eager work between the replays
+        call(lb_e, lt_e)
+        torch.cuda.synchronize()
+        assert kv.kvtrim_poll_error(ctx) == 0
+        assert torch.equal(lb_g.view(torch.int32), lb_e.view(torch.int32)), (n_tok, prepared, r)
+        assert torch.equal(lt_g.view(torch.int32), lt_e.view(torch.int32)), (n_tok, prepared, r)
