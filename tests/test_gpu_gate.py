@@ -123,9 +123,10 @@ def test_both_paths_agree_across_the_token_threshold():
     assert np.max(np.abs(got[127] - got[128][:127]) / np.abs(lb_ref[:127])) <= RTOL
 
 
-def test_initial_bias_of_eighteen_keeps_beta_next_to_one():
+@pytest.mark.parametrize("d_g,n_tok", [(64, 4), (128, 130)])     # per-token kernels; folded kernel
+def test_initial_bias_of_eighteen_keeps_beta_next_to_one(d_g, n_tok):
     # Sec. 5.1: b_g starts at 18.0 - log beta is about -1.5e-8 and must not flush to 0 or lose its digits
-    z_ref, lb_ref, _, lb, _ = run_both(2, 2, 256, 64, 16, 4, b_g=18.0)
+    z_ref, lb_ref, _, lb, _ = run_both(2, 2, 256, d_g, 16, n_tok, b_g=18.0)
     assert (lb < 0).all() and rel_err(lb, lb_ref) <= 2e-3 * np.max(np.abs(z_ref))   # d(log beta)/log beta = -dz here
 
 
