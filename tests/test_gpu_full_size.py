@@ -211,6 +211,9 @@ def test_long_128k_paged_steady_state():
         kv.kvtrim_paged_score(ctx, pc, torch.from_numpy(now).to(DEV), score)
         kv.kvtrim_paged_select(ctx, pc, score, budget, keep, kept, thr)
         kv.kvtrim_paged_evict(ctx, pc, keep)
+        if step == 2:                                             # pack the pages at full size; the checks below still hold
+            kv.kvtrim_paged_defrag(ctx, pc)
+            assert torch.equal(pc.seg_pages, (pc.seg_live + kv.PAGE_SIZE - 1) // kv.PAGE_SIZE)
         kv.kvtrim_paged_attn(ctx, pc, inp["q"], 0, w.n_layers, scale, out, lse)
         assert kv.kvtrim_poll_error(ctx) == 0
         oracle.append(hc, bf16_bits(inp["k_new"]), bf16_bits(inp["v_new"]), inp["log_beta_new"].cpu().numpy(), pos_new)
