@@ -180,10 +180,21 @@ def bench_chunk(args):
     per_seq = w.n_layers * w.n_kv_heads
     reserve = chunk
     B = sum(w.budget)
-    cap = B + nseg * reserve + 8
-    caches = [kv.Cache.empty(nseg, D, cap, dev) for _ in range(2)]
-    caches[0].seg_start.copy_(torch.arange(nseg, dtype=torch.int64) * reserve)
-    ctx = kv.Context(S, w.n_layers, w.n_kv_heads, w.n_q_heads, D, cap)
+    paged = args.paged
+    if paged:
+        # pages for the budget and the chunk that is live until the eviction, plus slack for partly filled pages
+        n_pages = (B + nseg * chunk) // kv.PAGE_SIZE + 3 * nseg + 64
+        cap = n_pages * kv.PAGE_SIZE
+        ctx = kv.Context(S, w.n_layers, w.n_kv_heads, w.n_q_heads, D, cap)
+        pc = kv.PagedCache(nseg, D, n_pages, n_pages, dev)
+        empty = kv.Cache.empty(nseg, D, 8, dev)                     # the pool is initialised from an empty ragged cache
+        kv.kvtrim_paged_build(ctx, empty, torch.zeros(8, dtype=torch.uint8, device=dev),
+                              torch.zeros(nseg, dtype=torch.int32, device=dev), pc)
+    else:
+        cap = B + nseg * reserve + 8
+        caches = [kv.Cache.empty(nseg, D, cap, dev) for _ in range(2)]
+        caches[0].seg_start.copy_(torch.arange(nseg, dtype=torch.int64) * reserve)
+        ctx = kv.Context(S, w.n_layers, w.n_kv_heads, w.n_q_heads, D, cap)
     score = torch.zeros(cap, dtype=torch.float32, device=dev)
     keep = torch.zeros(cap, dtype=torch.uint8, device=dev)
     kept = torch.zeros(nseg, dtype=torch.int32, device=dev)
@@ -200,6 +211,12 @@ def bench_chunk(args):
     state = {"cur": 0}
 
     def step(s):
+        if paged:
+            kv.kvtrim_paged_append(ctx, pc, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos_news[s], n_new=chunk)
+            kv.kvtrim_paged_score(ctx, pc, nows[s], score)
+            kv.kvtrim_paged_select(ctx, pc, score, budget, keep, kept, thr)
+            kv.kvtrim_paged_evict(ctx, pc, keep)
+            return
         cur, dst = caches[state["cur"]], caches[state["cur"] ^ 1]
         kv.kvtrim_append(ctx, cur, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos_news[s], chunk)
         kv.kvtrim_score(ctx, cur, nows[s], score)
@@ -227,24 +244,28 @@ def bench_chunk(args):
     for name, (t, n) in sorted(prof.items(), key=lambda kvp: -kvp[1][0]):
         log(f"[bench]   {name:16s} {t / n * 1e3:8.1f} us x {n}")
     R = 4 * D + 8
-    stage = {"append": 2 * R * nseg * chunk, "score": 8 * n_cand, "select": 5 * n_cand, "compact": 2 * R * n_ret}
+    stage = {"append": 2 * R * nseg * chunk, "score": 8 * n_cand, "select": 5 * n_cand,
+             "compact": 0 if paged else 2 * R * n_ret}              # pages: eviction frees slots, nothing moves
     total = sum(stage.values())
-    dom = "k_cmp_copy"
+    dom = "k_pg_append" if paged else "k_cmp_copy"
+    dom_bytes = stage["append"] if paged else stage["compact"]
     d_ms = prof[dom][0] / prof[dom][1]
-    log(f"[bench] chunk step: {ms:.3f} ms ({total / (ms * 1e-3) / 1e9:.0f} GB/s algorithmic end to end); {dom} {d_ms:.3f} ms "
-        f"({stage['compact'] / (d_ms * 1e-3) / 1e9:.0f} GB/s)")
+    log(f"[bench] chunk step{' on pages' if paged else ''}: {ms:.3f} ms ({total / (ms * 1e-3) / 1e9:.0f} GB/s algorithmic end "
+        f"to end); {dom} {d_ms:.3f} ms ({dom_bytes / (d_ms * 1e-3) / 1e9:.0f} GB/s)")
     print(json.dumps({
         "metric": "chunked-prefill steps/sec (append a chunk, rescore, select, compact), 16 sequences", "value": 1e3 / ms,
         "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"multiturn chunk step: S{S} L{w.n_layers} Hkv{w.n_kv_heads} D{D}, {chunk} new tokens per "
                                f"segment, {n_cand} candidates -> {n_ret} retained per step",
-                   "stages": "append, score, select_global, compact (no attention in a chunk step)"},
+                   "layout": "paged" if paged else "ragged",
+                   "stages": ("paged_append, paged_score, paged_select, paged_evict" if paged else
+                              "append, score, select_global, compact") + " (no attention in a chunk step)"},
         "end_to_end": {"algorithmic_bytes_per_step": total, "achieved_GBps": total / (ms * 1e-3) / 1e9,
                        "frac_of_hbm_peak": total / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "bytes_by_stage": stage},
-        "roofline": {"bound": "hbm", "kernel": dom, "achieved": stage["compact"] / (d_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": stage["compact"] / (d_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
-                     "algorithmic_bytes_per_launch": stage["compact"], "avg_launch_ms": d_ms},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": dom_bytes / (d_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": dom_bytes / (d_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": d_ms},
     }), flush=True)
 
 
