@@ -300,8 +300,7 @@ __global__ __launch_bounds__(PGA_THREADS) void k_pg_append_n(PagedView pc, const
 // Score: a block takes PG_PER_BLOCK pages; a thread takes four consecutive slots (16-byte loads
 // and stores).  Empty slots of a segment's pages get 0; free pages are skipped.
 constexpr int PG_PER_BLOCK = 8;
-constexpr int PG_THREADS = PG_PER_BLOCK * P;         // one thread per slot (eviction)
-constexpr int PG4_THREADS = PG_PER_BLOCK * P / 4;    // one thread per four slots (score, mask)
+constexpr int PG4_THREADS = PG_PER_BLOCK * P / 4;    // one thread per four slots
 
 __global__ __launch_bounds__(PG4_THREADS) void k_pg_score(PagedView pc, const int32_t* __restrict__ now,
                                                           float* __restrict__ score, int segs_per_seq, int nseg) {
@@ -699,19 +698,34 @@ __global__ __launch_bounds__(PGC_THREADS) void k_pg_count(PagedView pc, const fl
 }
 
 // ---------------------------------------------------------------------------------------------
-// Eviction: a block takes PG_PER_BLOCK pages, one thread per slot.  A page left without a live
-// entry is marked for release (owner -2); k_pg_tidy takes it out of its segment's block table
-// and pushes it on the free list.
-__global__ __launch_bounds__(PG_THREADS) void k_pg_evict(PagedView pc, const uint8_t* __restrict__ keep, int nseg) {
-    const int page = blockIdx.x * PG_PER_BLOCK + (threadIdx.x >> 7);
+// Eviction: a block takes PG_PER_BLOCK pages, a thread four consecutive slots (16-byte loads of the
+// positions, 4-byte loads of the mask), so a page is the business of one half wavefront.  A page left
+// without a live entry is marked for release (owner -2); k_pg_tidy takes it out of its segment's block
+// table and pushes it on the free list.
+__global__ __launch_bounds__(PG4_THREADS) void k_pg_evict(PagedView pc, const uint8_t* __restrict__ keep, int nseg) {
+    const int page = blockIdx.x * PG_PER_BLOCK + (threadIdx.x >> 5);
     const int owner = page < pc.n_pages ? pc.page_owner[page] : -1;
-    __syncthreads();                                                 // both wavefronts of a page have read its owner
-    if (owner < 0 || owner >= nseg) return;                          // uniform over the wavefront
-    const int64_t e = (int64_t)page * P + (threadIdx.x & (P - 1));
-    const bool ev = pc.pos[e] >= 0 && keep[e] == 0;
-    if (ev) pc.pos[e] = -1;
-    const int n = __popcll(__ballot(ev));
-    if (n && lane_id() == 0) {
+    const bool mine = owner >= 0 && owner < nseg;                    // the same in the 32 lanes of a page
+    int n = 0;
+    if (mine) {
+        const int64_t e = (int64_t)page * P + (threadIdx.x & 31) * 4;
+        int4 ps = *reinterpret_cast<const int4*>(pc.pos + e);
+        const uint32_t kp = *reinterpret_cast<const uint32_t*>(keep + e);
+        const bool e0 = ps.x >= 0 && (kp & 0x000000FFu) == 0, e1 = ps.y >= 0 && (kp & 0x0000FF00u) == 0;
+        const bool e2 = ps.z >= 0 && (kp & 0x00FF0000u) == 0, e3 = ps.w >= 0 && (kp & 0xFF000000u) == 0;
+        n = (int)e0 + (int)e1 + (int)e2 + (int)e3;
+        if (n) {
+            if (e0) ps.x = -1;
+            if (e1) ps.y = -1;
+            if (e2) ps.z = -1;
+            if (e3) ps.w = -1;
+            *reinterpret_cast<int4*>(pc.pos + e) = ps;
+        }
+    }
+    // sum over the 32 lanes of the page (the exchanges stay inside each half of the wavefront)
+#pragma unroll
+    for (int d = 16; d >= 1; d >>= 1) n += __shfl_xor(n, d, 64);
+    if (mine && n && (threadIdx.x & 31) == 0) {
         const int left = atomicSub(&pc.page_live[page], n) - n;
         atomicSub(&pc.seg_live[owner], n);
         if (left <= 0) pc.page_owner[page] = -2;
@@ -1032,11 +1046,12 @@ kvtrim_status kvtrim_paged_evict(kvtrim_ctx* ctx, kvtrim_paged_cache* c, const u
     if (!ctx) return KVTRIM_EINVAL;
     if (const char* p = paged_problem(ctx, c)) return bad(ctx, p);
     if (!keep) return bad(ctx, "keep is NULL");
+    if (((uintptr_t)keep) & 3) return bad(ctx, "keep not 4-byte aligned");
     hipStream_t st = (hipStream_t)hip_stream;
     const PagedView pv = view_of(c);
     {
         ProfScope prof(ctx, K_PG_EVICT, st);
-        hipLaunchKernelGGL(k_pg_evict, dim3((c->n_pages + PG_PER_BLOCK - 1) / PG_PER_BLOCK), dim3(PG_THREADS), 0, st, pv, keep,
+        hipLaunchKernelGGL(k_pg_evict, dim3((c->n_pages + PG_PER_BLOCK - 1) / PG_PER_BLOCK), dim3(PG4_THREADS), 0, st, pv, keep,
                            ctx->shape.nseg);
     }
     {
