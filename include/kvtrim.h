@@ -85,7 +85,11 @@ typedef struct {
 } kvtrim_cache;
 
 /* Context life cycle (host side, synchronous).  kvtrim_create allocates the
- * workspace on the current device; kvtrim_workspace_bytes says how large it is. */
+ * workspace on the current device; kvtrim_workspace_bytes says how large it is.
+ * One tuning knob is read from the environment at creation: KVTRIM_ATT_CHUNK = rows per
+ * split-K chunk of the stand-alone attention kernel (a multiple of 64 in [256, 65536];
+ * default 512, and larger for caches above 8 M entries so that at most 16384 full chunks
+ * exist).  It changes the order of floating-point sums in attention, nothing else. */
 kvtrim_status kvtrim_create(kvtrim_ctx **out, const kvtrim_config *cfg);
 kvtrim_status kvtrim_destroy(kvtrim_ctx *ctx);
 size_t kvtrim_workspace_bytes(const kvtrim_config *cfg);
