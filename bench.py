@@ -437,7 +437,7 @@ def main():
     log(f"[bench] first step (prefill -> budget): {first_ms:.3f} ms; steady state: {n_cand} candidates, {n_ret} retained")
 
     # ---- timed region: exactly K steps; the dominant kernels are bracketed by HIP events on the launch stream
-    mask = (1 << 8) | (1 << 10) | (1 << 13)   # k_cmp_copy, k_att_partial, k_cmp_attn
+    mask = (1 << 8) | (1 << 10) | (1 << 13) | (1 << 30)   # k_cmp_copy, k_att_partial, k_cmp_attn, k_att_fused
     if args.kernel_times:
         mask = (1 << kv.binding.N_KERNELS) - 1   # every kernel (the events then add to the step time)
     kv.kvtrim_profile_begin(ctx, mask)
@@ -489,6 +489,8 @@ def main():
         dom = "k_cmp_attn"
         dom_bytes = alg["compact"] + n_cand + 6 * w.head_dim * w.n_seq * w.n_layers * w.n_q_heads
         stage_model_bytes = alg["compact"] + alg["attend"]
+    if dom not in prof and "k_att_fused" in prof:   # large groups of query heads: the loop-shaped fused kernel, same bytes
+        dom = "k_att_fused"
     if dom not in prof:                       # the cache is too large for the fused kernel: the library ran the two stages
         dom, dom_bytes, stage_model_bytes = "k_cmp_copy", alg["compact"], None
     dom_ms, dom_n = prof[dom]

@@ -173,10 +173,11 @@ kvtrim_status kvtrim_occupancy(kvtrim_ctx *ctx, const kvtrim_cache *c, const int
 /* Stages 3 + 4 fused: exactly kvtrim_compact(src -> dst) followed by
  * kvtrim_decode_attn(dst), with the same arguments, results and device-side errors,
  * but every surviving K/V row is read from HBM once: it is used for the attention of
- * its segment while it is moved.  The library runs the two stages one after the other
- * instead - same results - where the fused kernel would not pay: more than 6 query heads
- * per KV head (5 at head_dim 64), a destination of less than a quarter of the source's
- * capacity (few rows can survive), or a source of more than 67 M entries. */
+ * its segment while it is moved.  Two kernels serve it: a one-shot one for up to 5 query
+ * heads per KV head (4 at head_dim 64), a loop-shaped one whose cost does not depend on the
+ * group for 5 ... 8.  The library runs the two stages one after the other instead - same
+ * results - where fusing would not pay: a destination of less than a quarter of the
+ * source's capacity (few rows can survive), or a source of more than 67 M entries. */
 kvtrim_status kvtrim_compact_attn(kvtrim_ctx *ctx, const kvtrim_cache *src, const uint8_t *keep,
                                   const int32_t *kept, kvtrim_cache *dst, int32_t reserve, const void *q,
                                   int32_t layer_begin, int32_t layer_end, float softmax_scale, float *out,
@@ -360,7 +361,7 @@ kvtrim_status kvtrim_gate_forward_prepared(kvtrim_ctx *ctx, const kvtrim_gate *g
  * end waits for `hip_stream` and writes, per kernel id, the summed duration in
  * milliseconds and the number of bracketed launches into host arrays of
  * KVTRIM_N_KERNELS elements.  Do not capture a HIP graph while profiling is on. */
-#define KVTRIM_N_KERNELS 30
+#define KVTRIM_N_KERNELS 31
 #define KVTRIM_PROFILE_MAX_LAUNCHES 4096
 kvtrim_status kvtrim_profile_begin(kvtrim_ctx *ctx, uint32_t kernel_mask);
 kvtrim_status kvtrim_profile_end(kvtrim_ctx *ctx, void *hip_stream, double *ms_sum_host,

@@ -20,7 +20,7 @@ EXPORTS = ["kvtrim_create", "kvtrim_destroy", "kvtrim_workspace_bytes", "kvtrim_
            "kvtrim_profile_begin", "kvtrim_profile_end",
            "kvtrim_kernel_name"]
 PAGE_SIZE = 128
-N_KERNELS = 30
+N_KERNELS = 31
 
 
 class KvtrimError(RuntimeError):

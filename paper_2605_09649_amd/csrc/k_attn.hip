@@ -260,6 +260,206 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
     }
 }
 
+// Stages 3 + 4 in one pass for groups of query heads too large for the one-shot fused kernel (its G x 8
+// output accumulators per lane have to fit next to a whole batch of rows): the split-K kernel above, reading
+// the SOURCE cache through the list of survivors of its 256-entry run and writing every row it has loaded to
+// the destination as well.  A run is two compaction chunks of one segment (ws.att_desc built over the source
+// with 256-entry chunks lines up with the 128-entry compaction table), so its survivors are contiguous in the
+// destination, from ws.cmp_chunk_dst of its first chunk on.  K travels in MFMA operand layout (loads and
+// stores of 16-byte pieces, lane = row), V and the metadata row by row; plain stores (non-temporal ones and a
+// second, row-wise load of K for coalesced stores both measured slower: 464 / 456 against 442 us).  Layers
+// outside [layer_begin, layer_end) are moved but not attended.
+constexpr int FUSE_RUN = 2 * CMP_CHUNK;      // source entries per block (a multiple of 256; 256 measured best: 426 us
+                                             // against 442 / 461 us for 512 / 1024 at 2.1 M entries and G = 8)
+
+template <int D, int G>
+__global__ __launch_bounds__(ATT_THREADS) void k_att_fused(CacheView src, const uint8_t* __restrict__ keep,
+                                                           CacheViewMut dst, const uint16_t* __restrict__ q, Shape sh,
+                                                           Workspace ws, float scale_log2, int layer_begin,
+                                                           int layer_end) {
+    typedef Frag<D> F;
+    typedef typename F::vec vec;
+    constexpr int E = F::E;
+    constexpr int NSTREAM = ATT_THREADS / 64;
+    constexpr int VPR = D / E;                                    // vectors per row = 16
+    __shared__ float s_m[NSTREAM][G], s_l[NSTREAM][G];
+    __shared__ float s_o[NSTREAM][G][D];
+    __shared__ int s_list[FUSE_RUN];
+    __shared__ int s_wcnt[FUSE_RUN / 64];
+
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    if (__hip_atomic_load(ws.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
+    const int total = ws.att_chunk_prefix[sh.nseg];
+    const int ch = blockIdx.x;
+    if (ch >= total) return;
+    const ChunkDesc cd = ws.att_desc[ch];
+    const int seg = cd.seg;
+    const int64_t sbase = cd.first;                               // first source entry of the run
+    const int cmp_ch = ws.cmp_chunk_prefix[seg] + (int)((sbase - src.seg_start[seg]) / CMP_CHUNK);
+    const int64_t dbase = ws.cmp_chunk_dst[cmp_ch];               // first destination entry of its survivors
+
+    // survivors of the run, in order: passes of 256 entries, ranks from ballots and wavefront counts
+    constexpr int NPASS = FUSE_RUN / ATT_THREADS;
+    bool flag[NPASS];
+    int rank[NPASS];
+#pragma unroll
+    for (int h = 0; h < NPASS; ++h) {
+        const int i = h * ATT_THREADS + tid;
+        flag[h] = i < cd.n && keep[sbase + i] != 0;
+        const uint64_t mask = __ballot(flag[h]);
+        rank[h] = mbcnt(mask);
+        if (lane == 0) s_wcnt[h * NSTREAM + wave] = __popcll(mask);
+    }
+    __syncthreads();
+    int cnt = 0;
+#pragma unroll
+    for (int w = 0; w < FUSE_RUN / 64; ++w) {
+        const int c = s_wcnt[w];
+#pragma unroll
+        for (int h = 0; h < NPASS; ++h)
+            if (w < h * NSTREAM + wave) rank[h] += c;
+        cnt += c;
+    }
+#pragma unroll
+    for (int h = 0; h < NPASS; ++h) {
+        if (flag[h]) {
+            const int i = h * ATT_THREADS + tid;
+            s_list[rank[h]] = i;
+            dst.log_beta[dbase + rank[h]] = src.log_beta[sbase + i];
+            if (src.log_tail) dst.log_tail[dbase + rank[h]] = src.log_tail[sbase + i];
+            dst.pos[dbase + rank[h]] = src.pos[sbase + i];
+        }
+    }
+    __syncthreads();
+
+    const int c16 = lane & 15, b4 = lane >> 4;
+    const int seq = seg / sh.segs_per_seq, lh = seg % sh.segs_per_seq;
+    const int layer = lh / sh.n_kv_heads, head = lh % sh.n_kv_heads;
+    const bool attend = layer >= layer_begin && layer < layer_end;   // uniform over the block
+    const int64_t qrow = ((int64_t)seq * sh.n_layers + layer) * sh.n_q_heads + (int64_t)head * G + c16;
+    vec qf[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        qf[j] = attend && c16 < G ? reinterpret_cast<const vec*>(q + qrow * D)[4 * j + b4] : F::zero();
+
+    float o[G][E];
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int e = 0; e < E; ++e) o[g][e] = 0.f;
+    float m = -INFINITY, l = 0.f;
+
+    const vec* kp = reinterpret_cast<const vec*>(src.k);
+    const vec* vp = reinterpret_cast<const vec*>(src.v);
+    vec* kd = reinterpret_cast<vec*>(dst.k);
+    vec* vd = reinterpret_cast<vec*>(dst.v);
+
+    for (int r0 = wave * 16; r0 < cnt; r0 += 64) {
+        const int last = cnt - 1;
+        // K in MFMA operand layout: lane -> survivor r0 + c16, vectors 4j + b4
+        const int kr = r0 + c16;
+        const int64_t ksrc = sbase + s_list[min(kr, last)];
+        vec kf[4], vf[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) kf[j] = kp[ksrc * VPR + 4 * j + b4];
+        // V row by row: lane -> survivor r0 + 4*b4 + i, vector c16
+#pragma unroll
+        for (int i = 0; i < 4; ++i) vf[i] = vp[(sbase + s_list[min(r0 + 4 * b4 + i, last)]) * VPR + c16];
+        if (kr < cnt) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) kd[(dbase + kr) * VPR + 4 * j + b4] = kf[j];
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = r0 + 4 * b4 + i;
+            if (row < cnt) vd[(dbase + row) * VPR + c16] = vf[i];
+        }
+        if (!attend) continue;
+
+        float4v acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc = F::mma(kf[j], qf[j], acc);
+        // acc[i] = q(c16) . k(survivor r0 + 4*b4 + i)
+        float z[4];
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            z[i] = r0 + 4 * b4 + i < cnt ? acc[i] * scale_log2 : -INFINITY;
+            tmax = fmaxf(tmax, z[i]);
+        }
+        const float m_new = fmaxf(m, tmax);
+        const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m - m_safe);   // m = -inf gives 0; l and o are 0 then
+        float p[4];
+        float psum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            p[i] = __builtin_amdgcn_exp2f(z[i] - m_safe);
+            psum += p[i];
+        }
+        l = l * alpha + psum;
+        m = m_new;
+        if (__any(alpha != 1.0f)) PV<G, E, 0>::scale(o, alpha);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float vfl[E];
+            F::unpack(vf[i], vfl);
+            PV<G, E, 0>::run(o, p[i], vfl);
+        }
+    }
+    if (!attend) return;
+
+    // merge as in k_att_partial: the four row-group streams of a wavefront, then the wavefronts through LDS
+    float m_all = fmaxf(m, __shfl_xor(m, 16, 64));
+    m_all = fmaxf(m_all, __shfl_xor(m_all, 32, 64));
+    const float m_fin = m_all == -INFINITY ? 0.f : m_all;
+    const float wgt = __builtin_amdgcn_exp2f(m - m_fin);          // 0 for a stream that saw no row
+    float l_all = l * wgt;
+    l_all += __shfl_xor(l_all, 16, 64);
+    l_all += __shfl_xor(l_all, 32, 64);
+    PV<G, E, 0>::scale(o, wgt);
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            float x = o[g][e];
+            x += __shfl_xor(x, 16, 64);
+            x += __shfl_xor(x, 32, 64);
+            o[g][e] = x;
+        }
+    if (b4 == 0) {
+        if (c16 < G) {
+            s_m[wave][c16] = m_all;
+            s_l[wave][c16] = l_all;
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int e = 0; e < E; ++e) s_o[wave][g][c16 * E + e] = o[g][e];
+    }
+    __syncthreads();
+    float* part = ws.att_partial + (size_t)ch * G * (D + 2);
+    for (int idx = tid; idx < G * D; idx += ATT_THREADS) {
+        const int g = idx / D, d = idx % D;
+        float M = -INFINITY;
+#pragma unroll
+        for (int s = 0; s < NSTREAM; ++s) M = fmaxf(M, s_m[s][g]);
+        const float Ms = M == -INFINITY ? 0.f : M;
+        float accd = 0.f, lsum = 0.f;
+#pragma unroll
+        for (int s = 0; s < NSTREAM; ++s) {
+            const float w = __builtin_amdgcn_exp2f(s_m[s][g] - Ms);
+            accd += s_o[s][g][d] * w;
+            lsum += s_l[s][g] * w;
+        }
+        part[g * (D + 2) + 2 + d] = accd;
+        if (d == 0) {
+            part[g * (D + 2)] = M;
+            part[g * (D + 2) + 1] = lsum;
+        }
+    }
+}
+
 // One block per segment of the layer range: merges the partial results of its chunks, a tile
 // of COMB_TILE chunks at a time.  Phase A brings the tile's (m, l) pairs into LDS and turns
 // them into weights 2^(m - M); phase B lets every thread sum "its" (query head, d) column over
@@ -400,6 +600,40 @@ kvtrim_status launch_attn(kvtrim_ctx* ctx, const CacheView& c, const uint16_t* q
     }
     if (!ok) return KVTRIM_EINVAL;
     return launch_combine(ctx, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, st);
+}
+
+// The loop-shaped fused pass for G > 4 (k_att_fused): the compaction tables must be in the workspace
+// (launch_cmp_scan); builds the run table over the source, moves every segment, attends the layer range.
+// Returns false when the group size has no instance.
+bool launch_attn_fused(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const CacheViewMut& dst,
+                       const uint16_t* q, int32_t layer_begin, int32_t layer_end, float scale, hipStream_t st) {
+    const Shape& sh = ctx->shape;
+    const Workspace& ws = ctx->ws;
+    const int64_t max_chunks = src.cap / FUSE_RUN + sh.nseg;
+    const float scale_log2 = scale * 1.4426950408889634f;
+    { ProfScope prof(ctx, K_ATT_PLAN, st);
+      hipLaunchKernelGGL(k_att_plan, dim3(1), dim3(1024), 0, st, src, sh, ws, FUSE_RUN, 0, sh.n_layers, max_chunks); }
+    ProfScope prof(ctx, K_ATT_FUSED, st);
+    const dim3 grid((unsigned)max_chunks), block(ATT_THREADS);
+#define KVTRIM_CASE(d, g) \
+    hipLaunchKernelGGL((k_att_fused<d, g>), grid, block, 0, st, src, keep, dst, q, sh, ws, scale_log2, layer_begin, layer_end); return true
+    if (sh.head_dim == 128) {
+        switch (sh.group) {
+            case 5: KVTRIM_CASE(128, 5);
+            case 6: KVTRIM_CASE(128, 6);
+            case 7: KVTRIM_CASE(128, 7);
+            case 8: KVTRIM_CASE(128, 8);
+            default: return false;
+        }
+    }
+    switch (sh.group) {
+        case 5: KVTRIM_CASE(64, 5);
+        case 6: KVTRIM_CASE(64, 6);
+        case 7: KVTRIM_CASE(64, 7);
+        case 8: KVTRIM_CASE(64, 8);
+        default: return false;
+    }
+#undef KVTRIM_CASE
 }
 
 // Attention over the page runs listed in ws.att_desc / ws.att_chunk_prefix (built by the paged plan

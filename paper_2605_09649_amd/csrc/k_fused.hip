@@ -285,9 +285,13 @@ static bool dispatch_fused(int G, dim3 grid, hipStream_t st, const CacheView& sr
     case g: hipLaunchKernelGGL((k_cmp_attn<D, g>), grid, dim3(FUS_THREADS), 0, st, src, keep, dst, q, sh, ws, scale_log2, lb, le); return true;
         KVTRIM_CASE(1) KVTRIM_CASE(2) KVTRIM_CASE(3) KVTRIM_CASE(4) KVTRIM_CASE(5) KVTRIM_CASE(6)
 #undef KVTRIM_CASE
-        default: return false;                                    // larger groups take the two-call path
+        default: return false;                                    // larger groups take the loop-shaped kernel (k_att_fused)
     }
 }
+
+// Largest group of query heads the one-shot fused kernel below is used for (beyond it, the loop-shaped one).
+constexpr int FUSED_ONE_SHOT_MAX_G_128 = 5, FUSED_ONE_SHOT_MAX_G_64 = 4;
+constexpr int FUSE_RUN_ENTRIES = 2 * CMP_CHUNK;                   // source entries per block of the loop-shaped fused kernel
 
 kvtrim_status launch_compact_attn(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const int32_t* kept,
                                   const CacheViewMut& dst, int32_t reserve, const uint16_t* q, int32_t layer_begin,
@@ -295,19 +299,27 @@ kvtrim_status launch_compact_attn(kvtrim_ctx* ctx, const CacheView& src, const u
     const Shape& sh = ctx->shape;
     const Workspace& ws = ctx->ws;
     const int64_t max_chunks = src.cap / CMP_CHUNK + sh.nseg;
-    // The fused kernel does q.k and p.v on the vector ALU with G query heads' worth of accumulators per lane: it
-    // stays bound by HBM up to G = 6 at head_dim 128 and G = 5 at head_dim 64 (2.1 M retained entries, head_dim
-    // 128: 363-440 us for G = 1..6 against 553-569 us for the two calls, but 804 / 863 us at G = 7 / 8, where the
-    // accumulators no longer fit the register file; head_dim 64: 183-254 us for G = 1..5 against 275-279 us, 292
-    // against 281 us at G = 6).  Above that the copy kernel plus the MFMA attention kernel are faster.
-    const bool alu_fits = sh.head_dim == 128 ? sh.group <= 6 : sh.group <= 5;
-    if (max_chunks > ws.max_att_chunks || dst.cap < src.cap / 4 || !alu_fits) {
+    // The one-shot fused kernel does q.k and p.v on the vector ALU with G query heads' worth of accumulators per lane:
+    // its time grows with G (2.1 M retained entries, head_dim 128: 363-404 us for G = 1..5, 443 us at G = 6, 804 /
+    // 863 us at G = 7 / 8, where the accumulators no longer fit the register file; head_dim 64: 184-227 us for
+    // G = 1..4, 255 us at G = 5).  The loop-shaped fused kernel (k_att_fused) takes 421-423 us at head_dim 128 and
+    // 242-247 us at head_dim 64 whatever the group, the two calls 553-578 us and 276-285 us.
+    const bool alu_fits = sh.head_dim == 128 ? sh.group <= FUSED_ONE_SHOT_MAX_G_128 : sh.group <= FUSED_ONE_SHOT_MAX_G_64;
+    const bool sparse = dst.cap < src.cap / 4;
+    if (!sparse && !alu_fits && sh.group >= 5 && src.cap / FUSE_RUN_ENTRIES + sh.nseg <= ws.max_att_chunks &&
+        max_chunks <= ws.max_cmp_chunks) {
+        // Large groups of query heads: the loop-shaped fused kernel (the split-K attention kernel reading the source
+        // through the survivor lists and writing the rows out as well), whose cost hardly depends on G.
+        launch_cmp_scan(ctx, src, keep, kept, dst, reserve, st);
+        if (!launch_attn_fused(ctx, src, keep, dst, q, layer_begin, layer_end, scale, st)) return KVTRIM_EINVAL;
+        return launch_combine(ctx, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, st);
+    }
+    if (max_chunks > ws.max_att_chunks || sparse || !alu_fits) {
         // Run the two stages one after the other, which computes the same thing: when there are too many source
-        // chunks for the partial-result buffer, when the group of query heads is too large (above), and when the
-        // destination is so much smaller than the source that few rows can survive (the first eviction after a
-        // long prefill: the fused kernel would launch one block and write one partial result per 128 source
-        // entries for a handful of survivors each - measured 5.4 ms against 3.0 ms for the two calls at 1
-        // survivor in 16).
+        // chunks for the partial-result buffer, and when the destination is so much smaller than the source that
+        // few rows can survive (the first eviction after a long prefill: a fused kernel would launch one block and
+        // write one partial result per 128 source entries for a handful of survivors each - measured 5.4 ms
+        // against 3.0 ms for the two calls at 1 survivor in 16).
         kvtrim_status rc = launch_compact(ctx, src, keep, kept, dst, reserve, st);
         if (rc != KVTRIM_OK) return rc;
         CacheView d;

@@ -215,7 +215,7 @@ static const char* const kernel_names[KVTRIM_N_KERNELS] = {
     "k_score", "k_sel_plan", "k_sel_hist<0>", "k_sel_hist<1>", "k_sel_hist<2>", "k_sel_count", "k_sel_mask",
     "k_cmp_scan", "k_cmp_copy", "k_att_plan", "k_att_partial", "k_att_combine", "k_append", "k_cmp_attn", "k_occupancy",
     "k_pg_init", "k_pg_append", "k_pg_score", "k_pg_plan", "k_pg_count", "k_pg_evict", "k_pg_tidy", "k_pg_att_plan", "k_gate_hidden", "k_gate_readout",
-    "k_gate_fold", "k_gate_prefill", "k_gate_retile", "k_pg_defrag", "k_gate_dot"};
+    "k_gate_fold", "k_gate_prefill", "k_gate_retile", "k_pg_defrag", "k_gate_dot", "k_att_fused"};
 
 const char* kvtrim_kernel_name(int32_t id) { return id >= 0 && id < KVTRIM_N_KERNELS ? kernel_names[id] : nullptr; }
 

@@ -125,12 +125,14 @@ def test_horizon_tail_must_be_consistent_between_caches():
                          torch.zeros(2, dtype=torch.int32, device=DEV), 1)
 
 
+@pytest.mark.parametrize("G,D", [(4, 128), (8, 128), (6, 64)])
 @pytest.mark.parametrize("roomy", [True, False])
-def test_fused_call_with_a_layer_range_and_sparse_mask(roomy):
+def test_fused_call_with_a_layer_range_and_sparse_mask(roomy, G, D):
     # compaction + attention in one call on a mask that keeps about one entry in five, layers [1, 3) only.  With a
-    # destination of at least a quarter of the source the fused kernel runs; with a tight one the library expects
-    # few survivors and runs the two stages one after the other - same results either way.
-    w = wl(2, 3, 2, 4, 128)
+    # destination of at least a quarter of the source a fused kernel runs (the one-shot one for small groups of query
+    # heads, the loop-shaped one for G = 8 at head_dim 128 and G = 6 at head_dim 64); with a tight one the library
+    # expects few survivors and runs the two stages one after the other - same results either way.
+    w = wl(2, 3, 2, G, D)
     rng = np.random.default_rng(21)
     seg_len = rng.integers(0, 2500, w.nseg)
     c, _ = ki.ragged_cache(w, seg_len, salt=21)
@@ -141,10 +143,10 @@ def test_fused_call_with_a_layer_range_and_sparse_mask(roomy):
     assert (dst_cap >= hc.cap // 4) == roomy
     dst_ref = oracle.compact(hc, keep_np, dst_cap, 2)
     q = ki.decode_inputs(w, 3)["q"]
-    scale = 1.0 / math.sqrt(128)
+    scale = 1.0 / math.sqrt(D)
     ref, ref_lse = oracle.attend(dst_ref, bf16_bits(q), scale)
-    ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, 128, hc.cap)
-    dst = kv.Cache.empty(w.nseg, 128, dst_cap, DEV)
+    ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, D, hc.cap)
+    dst = kv.Cache.empty(w.nseg, D, dst_cap, DEV)
     out = torch.full(ref.shape, 99.0, dtype=torch.float32, device=DEV)
     lse = torch.full(ref_lse.shape, 99.0, dtype=torch.float32, device=DEV)
     kv.kvtrim_compact_attn(ctx, kv.Cache.from_dict(c, DEV), torch.from_numpy(keep_np).to(DEV),
