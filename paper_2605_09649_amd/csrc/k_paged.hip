@@ -453,9 +453,9 @@ __global__ __launch_bounds__(1024) void k_pg_plan(PagedView pc, Shape sh, const 
                                                   Workspace ws, int32_t* __restrict__ kept_out,
                                                   uint32_t* __restrict__ thr_out, int hist_blocks) {
     if (blockIdx.x >= PG_TABLE_BLOCKS) {
-        const int n = 3 * HIST_REPLICAS * sh.n_seq * RADIX_BINS;
+        const int64_t n = (int64_t)3 * HIST_REPLICAS * sh.n_seq * RADIX_BINS;
         const int zb = blockIdx.x - PG_TABLE_BLOCKS, nzb = gridDim.x - PG_TABLE_BLOCKS;
-        for (int i = zb * blockDim.x + threadIdx.x; i < n; i += nzb * blockDim.x) ws.hist[i] = 0;
+        for (int64_t i = zb * blockDim.x + threadIdx.x; i < n; i += nzb * blockDim.x) ws.hist[i] = 0;
         return;
     }
     const int tid = threadIdx.x;
@@ -496,6 +496,7 @@ __global__ __launch_bounds__(1024) void k_pg_plan(PagedView pc, Shape sh, const 
         st.need_rank = 0;
         ws.sel[seq] = st;                                            // final slot (what the count and mask kernels read)
         ws.sel[sh.n_seq + seq] = st;                                 // state before the first digit
+        ws.seq_done[seq] = 0;
         if (thr_out) thr_out[seq] = 0xFFFFFFFFu;
     }
 }

@@ -21,10 +21,11 @@ constexpr int HIST_BLOCKS = HIST_BLOCKS_MAX;   // atomics meet on one address wh
 constexpr int PLAN_ZERO_BLOCKS = 8;   // extra blocks of the plan kernel that clear the histograms
 
 __global__ __launch_bounds__(1024) void k_sel_plan(CacheView c, Shape sh, const int64_t* __restrict__ budget,
-                                                   Workspace ws, int32_t* __restrict__ kept_out, int hist_blocks) {
+                                                   Workspace ws, int32_t* __restrict__ kept_out,
+                                                   uint32_t* __restrict__ thr_out, int hist_blocks) {
     if (blockIdx.x > 0) {                      // clear the (replicated) histograms of the three passes
-        const int n = 3 * HIST_REPLICAS * sh.n_seq * RADIX_BINS;
-        for (int i = (blockIdx.x - 1) * blockDim.x + threadIdx.x; i < n; i += (gridDim.x - 1) * blockDim.x)
+        const int64_t n = (int64_t)3 * HIST_REPLICAS * sh.n_seq * RADIX_BINS;   // 65536 sequences: 3.2 G words
+        for (int64_t i = (blockIdx.x - 1) * blockDim.x + threadIdx.x; i < n; i += (gridDim.x - 1) * blockDim.x)
             ws.hist[i] = 0;
         return;
     }
@@ -57,6 +58,8 @@ __global__ __launch_bounds__(1024) void k_sel_plan(CacheView c, Shape sh, const 
         st.need_rank = 0;
         ws.sel[seq] = st;                                         // final slot (what the count and mask kernels read)
         ws.sel[sh.n_seq + seq] = st;                              // state before the first digit
+        ws.seq_done[seq] = 0;
+        if (thr_out) thr_out[seq] = 0xFFFFFFFFu;                  // stands for a sequence that keeps nothing
     }
 }
 
@@ -201,33 +204,32 @@ __global__ __launch_bounds__(HIST_THREADS) void k_sel_hist(const float* __restri
                     h[i] = 0;
                 }
             }
-        }
-    }
-    if (PASS < 2) return;                                         // the next pass finds this pass's digit itself
+            if (PASS < 2) continue;                               // the next pass finds this pass's digit itself
 
-    __syncthreads();
-    if (tid == 0) is_last = arrive_last(ws.done + 32 * PASS);
-    __syncthreads();
-    if (!is_last) return;
-    __threadfence();
-
-    // Last block of the last pass: per sequence the final digit, hence the threshold key, how many of the
-    // entries equal to it survive, and whether those have to be ranked in order.
-    for (int seq = 0; seq < sh.n_seq; ++seq) {
-        if (ws.sel[seq].keep_none) {
-            if (tid == 0 && thr_out) thr_out[seq] = 0xFFFFFFFFu;
-            continue;
+            // Last pass: the block that is last to add its counts for THIS sequence takes the final digit, hence
+            // the threshold key, how many of the entries equal to it survive, and whether those have to be ranked
+            // in order.  (One "last block" per sequence, so the sequences of a batch finish side by side.)
+            __syncthreads();
+            if (tid == 0) {
+                __threadfence();
+                const int p0 = tb.prefix[seq * sh.segs_per_seq], p1 = tb.prefix[(seq + 1) * sh.segs_per_seq];
+                const int cpb = (tb.prefix[sh.nseg] + (int)gridDim.x - 1) / (int)gridDim.x;   // chunks per block, as in the plan
+                const unsigned nblk = (unsigned)((p1 - 1) / cpb - p0 / cpb + 1);              // blocks that meet [p0, p1)
+                is_last = atomicAdd(&ws.seq_done[seq], 1u) == nblk - 1;
+            }
+            __syncthreads();
+            if (!is_last) continue;
+            __threadfence();
+            SelState fin = next_digit<2>(hist_pass, sh.n_seq, seq, st, lds64, &s_state, &s_cnt);
+            if (tid == 0) {
+                fin.thr_key = fin.prefix;
+                fin.tie_quota = fin.rank;
+                fin.need_rank = fin.rank < (int64_t)s_cnt;        // fewer survive than tie at the threshold
+                if (fin.need_rank) atomicOr((int*)&ws.done[127], 1);
+                if (thr_out) thr_out[seq] = fin.thr_key;
+                ws.sel[seq] = fin;
+            }
         }
-        SelState st = next_digit<2>(hist_pass, sh.n_seq, seq, ws.sel[(size_t)3 * sh.n_seq + seq], lds64, &s_state, &s_cnt);
-        if (tid == 0) {
-            st.thr_key = st.prefix;
-            st.tie_quota = st.rank;
-            st.need_rank = st.rank < (int64_t)s_cnt;              // fewer survive than tie at the threshold
-            if (st.need_rank) atomicOr((int*)&ws.done[127], 1);
-            if (thr_out) thr_out[seq] = st.thr_key;
-            ws.sel[seq] = st;
-        }
-        __syncthreads();
     }
 }
 
@@ -382,7 +384,7 @@ kvtrim_status launch_select(kvtrim_ctx* ctx, const CacheView& c, const float* sc
     tb.prefix = ws.sel_chunk_prefix;
     tb.pos = nullptr;
     { ProfScope prof(ctx, K_SEL_PLAN, st);
-      hipLaunchKernelGGL(k_sel_plan, dim3(1 + PLAN_ZERO_BLOCKS), dim3(1024), 0, st, c, sh, budget, ws, kept, hist_blocks); }
+      hipLaunchKernelGGL(k_sel_plan, dim3(1 + PLAN_ZERO_BLOCKS), dim3(1024), 0, st, c, sh, budget, ws, kept, thr, hist_blocks); }
     { ProfScope prof(ctx, K_SEL_HIST0, st);
       hipLaunchKernelGGL((k_sel_hist<0, SEL_SHIFT, false>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr); }
     { ProfScope prof(ctx, K_SEL_HIST1, st);

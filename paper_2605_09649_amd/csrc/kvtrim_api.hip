@@ -80,6 +80,7 @@ static Layout layout_of(const kvtrim_config* c) {
     l.off[18] = bump(cur, (size_t)nseg * sizeof(int32_t));                     // tie_thr
     l.off[19] = bump(cur, (size_t)nseg * sizeof(int64_t));                     // pg_seg_start
     l.off[20] = bump(cur, (size_t)nseg * sizeof(int32_t));                     // pg_seg_len
+    l.off[21] = bump(cur, (size_t)c->n_seq * sizeof(uint32_t));                // seq_done
     l.total = (cur + 255) & ~(size_t)255;
     return l;
 }
@@ -191,6 +192,7 @@ kvtrim_status kvtrim_create(kvtrim_ctx** out, const kvtrim_config* cfg) {
     w.tie_thr = (int32_t*)(b + l.off[18]);
     w.pg_seg_start = (int64_t*)(b + l.off[19]);
     w.pg_seg_len = (int32_t*)(b + l.off[20]);
+    w.seq_done = (uint32_t*)(b + l.off[21]);
     w.max_sel_chunks = l.max_sel_chunks;
     w.max_cmp_chunks = l.max_cmp_chunks;
     w.max_att_chunks = l.max_att_chunks;

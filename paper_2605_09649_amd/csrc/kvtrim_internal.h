@@ -92,6 +92,7 @@ struct Workspace {
     int32_t* pg_seg_len;         // [nseg]
     uint32_t* hist;              // [3][HIST_REPLICAS][n_seq][RADIX_BINS]
     SelState* sel;               // [4][n_seq]: final state; state after the plan, after pass 0, after pass 1
+    uint32_t* seq_done;          // [n_seq] blocks of the last histogram pass that have added their counts for the sequence
     uint32_t* done;              // [DONE_WORDS] "last block" counters: per pass one top-level and 16 group counters
     int32_t* chunk_eq;           // [max_sel_chunks] entries equal to the threshold
     int64_t* chunk_tie_base;     // [max_sel_chunks] ties of the sequence before the chunk
