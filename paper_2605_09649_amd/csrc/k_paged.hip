@@ -591,35 +591,36 @@ __global__ __launch_bounds__(PGC_THREADS) void k_pg_count(PagedView pc, const fl
     __shared__ int64_t lds64[17];
     __shared__ int32_t lds32[17];
     __shared__ uint32_t h[2048];
-    __shared__ int is_last, s_part_seg, s_part_q, s_digit, s_rank;
+    __shared__ int s_list[PGC_THREADS];
+    __shared__ int s_n, is_last, s_part_seg, s_part_q, s_digit, s_rank;
     const int tid = threadIdx.x;
-    const int total = ws.cmp_chunk_prefix[sh.nseg];
-    for (int ch = blockIdx.x * 2 + (tid >> 7); ch < total; ch += gridDim.x * 2) {
-        const ChunkDesc d = ws.cmp_desc[ch];
-        const SelState st = ws.sel[d.seg / sh.segs_per_seq];
-        if (!st.need_rank) continue;                                 // uniform over the wavefront
-        const int64_t e = d.first + (tid & (P - 1));
-        bool gt = false, eq = false;
-        if (pc.pos[e] >= 0) {
-            const uint32_t key = key_of_score(score[e]);
-            gt = key > st.thr_key;
-            eq = key == st.thr_key;
+    for_each_ranked_seq(ws.sel, sh.n_seq, s_list, &s_n, [&](int seq) {
+        const uint32_t thr_key = ws.sel[seq].thr_key;
+        const int cb = ws.cmp_chunk_prefix[seq * sh.segs_per_seq], ce = ws.cmp_chunk_prefix[(seq + 1) * sh.segs_per_seq];
+        for (int ch = cb + blockIdx.x * 2 + (tid >> 7); ch < ce; ch += gridDim.x * 2) {   // uniform over the wavefront
+            const ChunkDesc d = ws.cmp_desc[ch];
+            const int64_t e = d.first + (tid & (P - 1));
+            bool gt = false, eq = false;
+            if (pc.pos[e] >= 0) {
+                const uint32_t key = key_of_score(score[e]);
+                gt = key > thr_key;
+                eq = key == thr_key;
+            }
+            const int ngt = __popcll(__ballot(gt)), neq = __popcll(__ballot(eq));
+            if (lane_id() == 0) {
+                if (ngt) atomicAdd(&kept_out[d.seg], ngt);
+                if (neq) atomicAdd(&ws.tie_cnt[d.seg], neq);
+            }
         }
-        const int ngt = __popcll(__ballot(gt)), neq = __popcll(__ballot(eq));
-        if (lane_id() == 0) {
-            if (ngt) atomicAdd(&kept_out[d.seg], ngt);
-            if (neq) atomicAdd(&ws.tie_cnt[d.seg], neq);
-        }
-    }
+    });
     __syncthreads();
     if (tid == 0) is_last = arrive_last(ws.done + 32 * 3);
     __syncthreads();
     if (!is_last) return;
     __threadfence();
 
-    for (int seq = 0; seq < sh.n_seq; ++seq) {
+    for_each_ranked_seq(ws.sel, sh.n_seq, s_list, &s_n, [&](int seq) {
         const SelState st = ws.sel[seq];
-        if (!st.need_rank) continue;
         if (tid == 0) s_part_seg = -1;
         __syncthreads();
         int64_t running = 0;
@@ -644,7 +645,7 @@ __global__ __launch_bounds__(PGC_THREADS) void k_pg_count(PagedView pc, const fl
         }
         __syncthreads();
         const int g = s_part_seg;
-        if (g < 0) continue;                                         // uniform over the block
+        if (g < 0) return;                                           // uniform over the block
         // the q-th smallest position among the ties of segment g: 11 + 10 + 10 bits, most significant first
         const int npg = pc.seg_pages[g];
         const int32_t* bt = pc.block_table + (int64_t)g * pc.max_pps;
@@ -695,7 +696,7 @@ __global__ __launch_bounds__(PGC_THREADS) void k_pg_count(PagedView pc, const fl
             atomicAdd(&kept_out[g], s_part_q);
         }
         __syncthreads();
-    }
+    });
 }
 
 // ---------------------------------------------------------------------------------------------

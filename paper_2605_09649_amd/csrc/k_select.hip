@@ -242,19 +242,20 @@ __global__ __launch_bounds__(CNT_THREADS) void k_sel_count(const float* __restri
                                                            int32_t* __restrict__ kept_out) {
     __shared__ int64_t lds64[17];
     __shared__ int32_t lds32[17];
-    __shared__ int is_last;
+    __shared__ int s_list[CNT_THREADS];
+    __shared__ int s_n, is_last;
     if (ws.done[127] == 0) return;                                // uniform over the grid
     const int tid = threadIdx.x;
-    const int total = tb.prefix[sh.nseg];
-    for (int ch = blockIdx.x; ch < total; ch += gridDim.x) {
-        const ChunkDesc d = tb.desc[ch];
-        const SelState st = ws.sel[d.seg / sh.segs_per_seq];
-        if (st.need_rank) {                                       // uniform over the block
+    for_each_ranked_seq(ws.sel, sh.n_seq, s_list, &s_n, [&](int seq) {
+        const uint32_t thr_key = ws.sel[seq].thr_key;
+        const int cb = tb.prefix[seq * sh.segs_per_seq], ce = tb.prefix[(seq + 1) * sh.segs_per_seq];
+        for (int ch = cb + blockIdx.x; ch < ce; ch += gridDim.x) {
+            const ChunkDesc d = tb.desc[ch];
             int gt = 0, eq = 0;
             for (int j = tid; j < d.n; j += CNT_THREADS) {
                 const uint32_t key = key_of_score(score[d.first + j]);
-                gt += key > st.thr_key;
-                eq += key == st.thr_key;
+                gt += key > thr_key;
+                eq += key == thr_key;
             }
             gt = block_sum<int32_t>(gt, lds32);
             eq = block_sum<int32_t>(eq, lds32);
@@ -263,15 +264,14 @@ __global__ __launch_bounds__(CNT_THREADS) void k_sel_count(const float* __restri
                 ws.chunk_eq[ch] = eq;
             }
         }
-    }
+    });
     __syncthreads();
     if (tid == 0) is_last = arrive_last(ws.done + 32 * 3);
     __syncthreads();
     if (!is_last) return;
     __threadfence();
 
-    for (int seq = 0; seq < sh.n_seq; ++seq) {
-        if (!ws.sel[seq].need_rank) continue;
+    for_each_ranked_seq(ws.sel, sh.n_seq, s_list, &s_n, [&](int seq) {
         const int cb = tb.prefix[seq * sh.segs_per_seq];
         const int ce = tb.prefix[(seq + 1) * sh.segs_per_seq];
         const int64_t quota = ws.sel[seq].tie_quota;
@@ -291,7 +291,7 @@ __global__ __launch_bounds__(CNT_THREADS) void k_sel_count(const float* __restri
             }
             running += tot;
         }
-    }
+    });
 }
 
 // keep[e] = key > thr, or key == thr and the entry is among the first `quota` ties of its

@@ -69,6 +69,25 @@ __device__ __forceinline__ bool arrive_last(uint32_t* counters) {
     return atomicAdd(&counters[0], 1u) == ngroups - 1;
 }
 
+// Calls body(seq) - by all threads of the block, one sequence after the other - for every sequence whose ties at
+// the threshold have to be ranked (need_rank in its final selection state).  The flags of blockDim.x sequences
+// are read at once, so a batch of many sequences of which few (usually none) need it costs one round of loads
+// instead of one dependent load per sequence.  s_list needs blockDim.x elements.
+template <typename Body>
+__device__ __forceinline__ void for_each_ranked_seq(const SelState* __restrict__ sel, int n_seq, int* s_list, int* s_n,
+                                                    Body body) {
+    for (int base = 0; base < n_seq; base += blockDim.x) {
+        __syncthreads();
+        if (threadIdx.x == 0) *s_n = 0;
+        __syncthreads();
+        const int sq = base + threadIdx.x;
+        if (sq < n_seq && sel[sq].need_rank) s_list[atomicAdd(s_n, 1)] = sq;
+        __syncthreads();
+        const int n = *s_n;
+        for (int k = 0; k < n; ++k) body(s_list[k]);
+    }
+}
+
 // Chunk table of a ragged cache, built by ONE block (blockDim.x <= 1024): segment g with
 // in_range(g) is cut into ceil(seg_len[g] / chunk) chunks (none for the other segments);
 // prefix[g] = first chunk of segment g, prefix[nseg] = number of chunks, desc[c] = entries and
