@@ -9,9 +9,9 @@
 // Both layers are dense contractions and run on the matrix cores (MFMA 16x16x32 bf16, fp32
 // accumulation); with one token per sequence they are bound by streaming the weights once from
 // HBM, and the unused token columns of the MFMA tile cost nothing.
-//   k_gate_hidden   a block owns 16 rows of W1 of one layer and up to 64 tokens; its four
-//                   wavefronts split the contraction over d_model, are summed through LDS, and
-//                   write u in fp32.
+//   k_gate_hidden   a block owns 16 rows of W1 of one layer (64 rows when a call brings more than 16
+//                   tokens) and up to 64 tokens; its four wavefronts split the contraction over
+//                   d_model, are summed through LDS, and write u in fp32.
 //   k_gate_readout  a block owns one (layer, head) and 16 tokens; u is split into two bf16 numbers
 //                   (u = hi + lo to 2^-17 relative) so that the second layer keeps fp32-like
 //                   accuracy on the bf16 matrix cores; every wavefront takes 16-row tiles of W2,
@@ -45,26 +45,30 @@ constexpr int GH_THREADS = 256;          // four wavefronts split d_model
 constexpr int GH_ROWS = 16;
 
 // x: bf16 [layers of the range][n_tok][d_model]; u: fp32 [layers of the range][n_tok][d_g]
+// NT: 16-token tiles per block; MT: 16-row tiles of W1 per block.  Every wavefront load of x fetches an operand
+// straight from row-major memory, the slow way through the vector L1, and every block reads all of its tokens'
+// rows: with more than 16 tokens a block takes MT = 4 tiles of W1 so that x is read by a quarter of the blocks.
 // TILED: W1 comes from the operand-order copy of a prepared buffer (`tiled` points at the first layer of the
 // range: [layer][16-row tile][64-wide step][half][lane] 16-byte pieces), so a wavefront load reads 1 KB in one piece.
-template <int NT, bool TILED>
+template <int NT, int MT, bool TILED>
 __global__ __launch_bounds__(GH_THREADS) void k_gate_hidden(GateView g, const uint16_t* __restrict__ x, int n_tok,
                                                             int layer_begin, const uint4* __restrict__ tiled,
                                                             float* __restrict__ u) {
-    __shared__ float s_part[4][NT][16][17];
+    __shared__ float s_part[4][NT][16 * MT][17];
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int r16 = lane & 15, g4 = lane >> 4;
-    const int row0 = blockIdx.x * GH_ROWS;
+    const int row0 = blockIdx.x * GH_ROWS * MT;
     const int lr = blockIdx.y;                                       // layer of the range
     const int layer = layer_begin + lr;
     const int tok0 = blockIdx.z * 16 * NT;
     const int kw = g.d_model >> 2;                                   // contraction share of a wavefront
     const int k_begin = wave * kw;
 
-    // piece p (0, 1) of step s sits at arow[s * a_step + p * a_half]
-    const uint4* arow = TILED ? tiled + (((size_t)lr * (g.d_g >> 4) + blockIdx.x) * (g.d_model >> 6) + (k_begin >> 6)) * 128 + lane
+    // piece p (0, 1) of step s of row tile m sits at arow[m * a_tile + s * a_step + p * a_half]
+    const uint4* arow = TILED ? tiled + (((size_t)lr * (g.d_g >> 4) + (size_t)blockIdx.x * MT) * (g.d_model >> 6) + (k_begin >> 6)) * 128 + lane
                               : reinterpret_cast<const uint4*>(g.w1 + ((size_t)layer * g.d_g + row0 + r16) * g.d_model + k_begin + 16 * g4);
     constexpr int a_step = TILED ? 128 : 8, a_half = TILED ? 64 : 1;
+    const size_t a_tile = TILED ? (size_t)(g.d_model >> 6) * 128 : (size_t)2 * g.d_model;
     const uint4* brow[NT];
     bool bval[NT];
 #pragma unroll
@@ -73,22 +77,27 @@ __global__ __launch_bounds__(GH_THREADS) void k_gate_hidden(GateView g, const ui
         bval[t] = tok < n_tok;
         brow[t] = reinterpret_cast<const uint4*>(x + ((size_t)lr * n_tok + (bval[t] ? tok : 0)) * g.d_model + k_begin + 16 * g4);
     }
-    gate_f4 acc[NT];
+    gate_f4 acc[MT][NT];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) acc[t] = gate_f4{0.f, 0.f, 0.f, 0.f};
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[m][t] = gate_f4{0.f, 0.f, 0.f, 0.f};
 
-    // 64 contraction indices per step (8 uint4 of a row); four steps of weights are loaded ahead
-    constexpr int AHEAD = 4;
+    // 64 contraction indices per step (8 uint4 of a row); AHEAD steps of weights are loaded ahead
+    constexpr int AHEAD = MT == 1 ? 4 : 2;
     const int steps = kw >> 6;                                       // kw is a multiple of 64
     for (int s0 = 0; s0 < steps; s0 += AHEAD) {
-        uint4 a[AHEAD][2];
+        uint4 a[AHEAD][MT][2];
 #pragma unroll
         for (int i = 0; i < AHEAD; ++i) {
-            if (s0 + i < steps) {
-                a[i][0] = arow[(s0 + i) * a_step];
-                a[i][1] = arow[(s0 + i) * a_step + a_half];
-            } else {
-                a[i][0] = a[i][1] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                if (s0 + i < steps) {
+                    a[i][m][0] = arow[m * a_tile + (s0 + i) * a_step];
+                    a[i][m][1] = arow[m * a_tile + (s0 + i) * a_step + a_half];
+                } else {
+                    a[i][m][0] = a[i][m][1] = make_uint4(0, 0, 0, 0);
+                }
             }
         }
 #pragma unroll
@@ -101,20 +110,26 @@ __global__ __launch_bounds__(GH_THREADS) void k_gate_hidden(GateView g, const ui
                         b0 = brow[t][(s0 + i) * 8];
                         b1 = brow[t][(s0 + i) * 8 + 1];
                     }
-                    acc[t] = mma_bf16(a[i][0], b0, acc[t]);
-                    acc[t] = mma_bf16(a[i][1], b1, acc[t]);
+#pragma unroll
+                    for (int m = 0; m < MT; ++m) {
+                        acc[m][t] = mma_bf16(a[i][m][0], b0, acc[m][t]);
+                        acc[m][t] = mma_bf16(a[i][m][1], b1, acc[m][t]);
+                    }
                 }
             }
         }
     }
-    // acc[t][r] = partial of (row 4*g4 + r, token r16 of tile t)
+    // acc[m][t][r] = partial of (row 16*m + 4*g4 + r, token r16 of tile t)
 #pragma unroll
-    for (int t = 0; t < NT; ++t)
+    for (int m = 0; m < MT; ++m)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) s_part[wave][t][4 * g4 + r][r16] = acc[t][r];
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) s_part[wave][t][16 * m + 4 * g4 + r][r16] = acc[m][t][r];
     __syncthreads();
-    for (int idx = tid; idx < NT * 256; idx += GH_THREADS) {
-        const int t = idx >> 8, tk = (idx >> 4) & 15, row = idx & 15;
+    constexpr int ROWS = 16 * MT;
+    for (int idx = tid; idx < NT * 16 * ROWS; idx += GH_THREADS) {
+        const int row = idx % ROWS, tk = (idx / ROWS) & 15, t = idx / (16 * ROWS);
         const int tok = tok0 + 16 * t + tk;
         if (tok < n_tok) {
             const float a = s_part[0][t][row][tk] + s_part[1][t][row][tk] + s_part[2][t][row][tk] + s_part[3][t][row][tk] +
@@ -714,7 +729,7 @@ kvtrim_status launch_gate(kvtrim_ctx* ctx, const GateView& g, const float* prepa
                                          (size_t)layer_begin * (g.d_g >> 4) * (g.d_model >> 6) * 128
                                    : nullptr;
     // with prepared weights the folded kernel has no per-call passes to pay for and wins from 24 tokens on
-    // (measured: 16 tokens 54 us per-token kernels / 58 us folded, 32 tokens 70 / 59, 64 tokens 104 / 58)
+    // (measured: 17 tokens 55 us per-token kernels, 24 tokens 58 / 58 us folded, 32 tokens 60 / 58, 64 tokens 80 / 58)
     if (n_tok >= (prepared ? GP_MIN_TOK_PREPARED : GP_MIN_TOK) && prefill_shape(ctx, g)) {
         const float* v = pv;
         const float* sconst = ps;
@@ -777,20 +792,19 @@ kvtrim_status launch_gate(kvtrim_ctx* ctx, const GateView& g, const float* prepa
     {
         ProfScope prof(ctx, K_GATE_HIDDEN, st);
         const dim3 grid1(g.d_g / GH_ROWS, nl, 1);
+        const dim3 grid4(g.d_g / (4 * GH_ROWS), nl, 1);              // d_g is a multiple of 64
         if (n_tok <= 16 && prepared)
-            hipLaunchKernelGGL((k_gate_hidden<1, true>), dim3(grid1.x, nl, 1), dim3(GH_THREADS), 0, st, g, x, n_tok, layer_begin,
-                               ptiled, scratch);
+            hipLaunchKernelGGL((k_gate_hidden<1, 1, true>), grid1, dim3(GH_THREADS), 0, st, g, x, n_tok, layer_begin, ptiled, scratch);
         else if (n_tok <= 32 && prepared)
-            hipLaunchKernelGGL((k_gate_hidden<2, true>), dim3(grid1.x, nl, 1), dim3(GH_THREADS), 0, st, g, x, n_tok, layer_begin,
-                               ptiled, scratch);
+            hipLaunchKernelGGL((k_gate_hidden<2, 4, true>), grid4, dim3(GH_THREADS), 0, st, g, x, n_tok, layer_begin, ptiled, scratch);
+        else if (n_tok <= 64 && prepared)
+            hipLaunchKernelGGL((k_gate_hidden<4, 4, true>), grid4, dim3(GH_THREADS), 0, st, g, x, n_tok, layer_begin, ptiled, scratch);
         else if (n_tok <= 16)
-            hipLaunchKernelGGL((k_gate_hidden<1, false>), dim3(grid1.x, nl, 1), dim3(GH_THREADS), 0, st, g, x, n_tok, layer_begin,
-                               ptiled, scratch);
+            hipLaunchKernelGGL((k_gate_hidden<1, 1, false>), grid1, dim3(GH_THREADS), 0, st, g, x, n_tok, layer_begin, ptiled, scratch);
         else if (n_tok <= 32)
-            hipLaunchKernelGGL((k_gate_hidden<2, false>), dim3(grid1.x, nl, 1), dim3(GH_THREADS), 0, st, g, x, n_tok, layer_begin,
-                               ptiled, scratch);
+            hipLaunchKernelGGL((k_gate_hidden<2, 4, false>), grid4, dim3(GH_THREADS), 0, st, g, x, n_tok, layer_begin, ptiled, scratch);
         else if (n_tok < 256)                                        // below that the tiled kernel cannot fill the chip
-            hipLaunchKernelGGL((k_gate_hidden<4, false>), dim3(grid1.x, nl, (n_tok + 63) / 64), dim3(GH_THREADS), 0, st, g, x, n_tok,
+            hipLaunchKernelGGL((k_gate_hidden<4, 4, false>), dim3(grid4.x, nl, (n_tok + 63) / 64), dim3(GH_THREADS), 0, st, g, x, n_tok,
                                layer_begin, ptiled, scratch);
         else
             hipLaunchKernelGGL(k_gate_hidden_gemm, dim3((g.d_g + GG_BM - 1) / GG_BM, (n_tok + GG_BN - 1) / GG_BN, nl), dim3(256), 0,
