@@ -22,7 +22,9 @@
  *    the kernel that finds the condition writes nothing out of bounds, and later
  *    kernels of the same call return early.  kvtrim_poll_error reads and clears it.
  *  - A context owns one workspace (allocated in kvtrim_create) that every call
- *    reuses: calls on one context must be ordered on one stream.
+ *    reuses: calls on one context must be ordered on one stream and come from one
+ *    host thread at a time (the context also keeps the last error text and the
+ *    profiling state without locks).  Different contexts are independent.
  *
  * Ragged cache (kvtrim_cache)
  *  A "segment" is the logical KV list of one (sequence, layer, KV head); segment
