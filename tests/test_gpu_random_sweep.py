@@ -64,3 +64,30 @@ def test_random_configuration(seed):
         assert r["structure"] == [] and r.get("structure_pre", []) == [], (seed, r)
         assert r["score_equal"] and r["keep_equal"] and r["kept_equal"] and r["cache_equal"], (seed, r)
         assert r["attn_err"] <= ATTN_TOL and r["lse_err"] <= 2e-3 and r["lse_inf_equal"], (seed, r)
+
+
+@pytest.mark.parametrize("S,L,H", [(600, 1, 2), (1100, 1, 1)])
+def test_many_short_sequences(S, L, H):
+    """Hundreds of sequences of a few dozen entries: a histogram block then holds several whole sequences, a
+    sequence's last block is found per sequence, and ties at the threshold (quantised log beta) have to be ranked
+    in many sequences of the same call."""
+    rng = np.random.default_rng(77 + S)
+    w = ki.Workload("m", 0, S, L, H, 2 * H, 64, (0,) * S, (0,) * S, 1, 3.0, 1.5)
+    seg_len = rng.integers(0, 41, w.nseg)
+    seg_len[rng.random(w.nseg) < 0.1] = 0
+    c, now = ki.ragged_cache(w, seg_len, reserve=1, salt=S, pos_stride_max=2)
+    g = torch.Generator().manual_seed(S)
+    c["log_beta"] = -(torch.randint(0, 3, c["log_beta"].shape, generator=g).to(torch.float32)) * 0.25
+    per_seq = [int(seg_len[s * L * H:(s + 1) * L * H].sum()) for s in range(S)]
+    budgets = [[0 if rng.random() < 0.05 else int(rng.integers(1, max(2, n + 3))) for n in per_seq] for _ in range(2)]
+    clone = lambda: {k: (v.clone() if torch.is_tensor(v) else v) for k, v in c.items()}
+    res = run_steps_both(w, steps=2, budget=budgets[0], device=DEV, cache_dict=clone(), now0=now.numpy(), fused=True)
+    for i, r in enumerate(res):
+        assert r["status"] == 0 and r["score_equal"] and r["keep_equal"] and r["cache_equal"], (S, i, r)
+        assert r["attn_err"] <= ATTN_TOL and r["lse_err"] <= 2e-3 and r["lse_inf_equal"], (S, i, r)
+    res = run_paged_both(w, budgets, device=DEV, cache_dict=clone(), now0=now.numpy())
+    for r in res:
+        assert r["status"] == 0 and r.get("status_select", 0) == 0, (S, r)
+        assert r["structure"] == [] and r.get("structure_pre", []) == [], (S, r)
+        assert r["score_equal"] and r["keep_equal"] and r["kept_equal"] and r["cache_equal"], (S, r)
+        assert r["attn_err"] <= ATTN_TOL and r["lse_err"] <= 2e-3 and r["lse_inf_equal"], (S, r)
