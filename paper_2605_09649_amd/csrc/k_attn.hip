@@ -296,7 +296,7 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_fused(CacheView src, const 
     const int seg = cd.seg;
     const int64_t sbase = cd.first;                               // first source entry of the run
     const int cmp_ch = ws.cmp_chunk_prefix[seg] + (int)((sbase - src.seg_start[seg]) / CMP_CHUNK);
-    const int64_t dbase = ws.cmp_chunk_dst[cmp_ch];               // first destination entry of its survivors
+    const int64_t dbase = ws.cmp_chunk_dst[cmp_ch] & ~CMP_DST_FULL;   // first destination entry of its survivors
 
     // survivors of the run, in order: passes of 256 entries, ranks from ballots and wavefront counts
     constexpr int NPASS = FUSE_RUN / ATT_THREADS;

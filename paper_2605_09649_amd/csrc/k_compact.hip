@@ -160,7 +160,9 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const 
         const int64_t v = ch < nch ? ws.cmp_chunk_dst[cbase + ch] : 0;
         int64_t tot;
         const int64_t ex = block_excl_scan<int64_t>(v, lds64, &tot);
-        if (ch < nch) ws.cmp_chunk_dst[cbase + ch] = dst_before + running + ex;
+        // a chunk that loses nothing is marked: its mover needs neither the mask nor the ranks
+        if (ch < nch)
+            ws.cmp_chunk_dst[cbase + ch] = (dst_before + running + ex) | (v == min(CMP_CHUNK, len - ch * CMP_CHUNK) ? CMP_DST_FULL : 0);
         running += tot;
     }
     if (tid == 0) {
@@ -200,7 +202,7 @@ __global__ __launch_bounds__(CMP_THREADS) void k_cmp_copy(CacheView src, const u
     if (ch >= total) return;
     const ChunkDesc d = ws.cmp_desc[ch];
     const int64_t sbase = d.first;                                // first source entry of the chunk
-    const int64_t dbase = ws.cmp_chunk_dst[ch];                   // first destination entry of its survivors
+    const int64_t dbase = ws.cmp_chunk_dst[ch] & ~CMP_DST_FULL;   // first destination entry of its survivors
     // the first CMP_CHUNK threads rank the survivors
     int rank = 0;
     bool flag = false;

@@ -12,6 +12,7 @@ constexpr int SEL_CHUNK = 2048;      // selection: entries per chunk
 constexpr int SEL_SHIFT = 11;        // log2(SEL_CHUNK)
 static_assert((1 << SEL_SHIFT) == SEL_CHUNK, "SEL_SHIFT out of step with SEL_CHUNK");
 constexpr int CMP_CHUNK = 128;       // compaction: entries per block
+constexpr long long CMP_DST_FULL = 1ll << 62;   // flag in ws.cmp_chunk_dst: every entry of the chunk survives
 constexpr int CMP_WAVE_ROWS = 16;    // rows a wavefront moves (one batch of loads, one of stores)
 constexpr int CMP_THREADS = CMP_CHUNK / CMP_WAVE_ROWS * 64;   // 512: one wavefront per 16 survivors
 constexpr int RADIX_BITS0 = 11, RADIX_BITS1 = 11, RADIX_BITS2 = 10;
@@ -99,7 +100,7 @@ struct Workspace {
     // compaction
     int32_t* cmp_chunk_prefix;   // [nseg+1]
     ChunkDesc* cmp_desc;         // [max_cmp_chunks]
-    int64_t* cmp_chunk_dst;      // [max_cmp_chunks] first dst entry of the chunk's survivors
+    int64_t* cmp_chunk_dst;      // [max_cmp_chunks] first dst entry of the chunk's survivors (| CMP_DST_FULL)
     // attention
     int32_t* att_chunk_prefix;   // [nseg+1]
     ChunkDesc* att_desc;         // [max_att_chunks]
