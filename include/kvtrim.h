@@ -200,6 +200,24 @@ kvtrim_status kvtrim_append(kvtrim_ctx *ctx, kvtrim_cache *c, const void *k_new,
                             const float *log_beta_new, const float *log_tail_new, const int32_t *pos_new,
                             int32_t n_new, void *hip_stream);
 
+/* A chunk of a prefill on the ragged layout in one call (the multi-turn flow of Sec. 4.2 / Sec. 5:
+ * after every appended chunk of tokens the cache is rescored, selected and compacted).  Leaves in
+ * score_out, keep_out, kept_out, thr_key_out and dst exactly what
+ *     kvtrim_append(src, new tokens) -> kvtrim_score(src, now) -> kvtrim_select_global(src, budget)
+ *     -> kvtrim_compact(src -> dst, reserve)
+ * leave there, but the K/V rows of the new tokens go from k_new / v_new straight to their places
+ * in dst: only their metadata is appended to src (the score and the selection read nothing else),
+ * so the chunk's K/V is written once instead of twice and read once instead of twice.
+ * Arguments as in those four calls.  src needs the free slots kvtrim_append needs; afterwards
+ * its metadata and seg_len include the new tokens and the K/V rows of those slots are
+ * unspecified: src is spent, the live cache is dst.  Device-side errors as in the four calls. */
+kvtrim_status kvtrim_append_compact(kvtrim_ctx *ctx, kvtrim_cache *src, const void *k_new, const void *v_new,
+                                    const float *log_beta_new, const float *log_tail_new,
+                                    const int32_t *pos_new, int32_t n_new, const int32_t *now,
+                                    const int64_t *budget, float *score_out, uint8_t *keep_out,
+                                    int32_t *kept_out, uint32_t *thr_key_out, kvtrim_cache *dst,
+                                    int32_t reserve, void *hip_stream);
+
 /* ------------------------------------------------------------------------------------
  * Paged variant: the layout of Sec. 4.2 "Implementation details" itself.  KV entries live
  * in fixed-size pages of KVTRIM_PAGE_SIZE slots; every (sequence, layer, KV head) segment

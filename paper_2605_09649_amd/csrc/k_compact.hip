@@ -187,9 +187,15 @@ __device__ __forceinline__ void st16_nt(uint4* p, uint4 v) {
     __builtin_nontemporal_store(t, reinterpret_cast<v4u*>(p));
 }
 
-template <int D>
+// NEW: the K/V rows of a segment's entries from old_len[seg] on are not in src but in k_new / v_new
+// ([nseg][n_new][D], entry old_len + i of segment g = row g * n_new + i): a chunk of tokens whose metadata has
+// been appended to src goes from the caller's buffers straight to its place in dst.
+template <int D, bool NEW>
 __global__ __launch_bounds__(CMP_THREADS) void k_cmp_copy(CacheView src, const uint8_t* __restrict__ keep,
-                                                          CacheViewMut dst, Shape sh, Workspace ws) {
+                                                          CacheViewMut dst, Shape sh, Workspace ws,
+                                                          const uint16_t* __restrict__ k_new,
+                                                          const uint16_t* __restrict__ v_new, int n_new,
+                                                          const int32_t* __restrict__ old_len) {
     constexpr int VPR = D / 8;                    // 16-byte vectors per row
     constexpr int RPI = 64 / VPR;                 // rows moved by one wavefront instruction
     constexpr int BATCH = CMP_WAVE_ROWS / RPI;    // instructions per wavefront: 4 (D=128) or 2 (D=64)
@@ -234,12 +240,23 @@ __global__ __launch_bounds__(CMP_THREADS) void k_cmp_copy(CacheView src, const u
     uint4* dv = reinterpret_cast<uint4*>(dst.v);
     const int sub = lane / VPR, col = lane % VPR;
     uint4 kk[BATCH], vv[BATCH];
+    // NEW: index of the chunk's first entry in its segment, and where the segment's new entries begin
+    const int64_t seg_off = NEW ? sbase - src.seg_start[d.seg] : 0;
+    const int64_t first_new = NEW ? old_len[d.seg] : 0;
+    const int64_t new_base = NEW ? (int64_t)d.seg * n_new - first_new : 0;   // + index in the segment = row of k_new
 #pragma unroll
     for (int u = 0; u < BATCH; ++u) {
         const int r = min(r0 + u * RPI + sub, cnt - 1);           // clamped: loads stay on live rows
-        const int64_t se = (sbase + list[r]) * VPR + col;
-        kk[u] = ld16_nt(sk + se);
-        vv[u] = ld16_nt(sv + se);
+        const int64_t j = seg_off + list[r];
+        if (NEW && j >= first_new) {
+            const int64_t ne = (new_base + j) * VPR + col;
+            kk[u] = ld16_nt(reinterpret_cast<const uint4*>(k_new) + ne);
+            vv[u] = ld16_nt(reinterpret_cast<const uint4*>(v_new) + ne);
+        } else {
+            const int64_t se = (sbase + list[r]) * VPR + col;
+            kk[u] = ld16_nt(sk + se);
+            vv[u] = ld16_nt(sv + se);
+        }
     }
 #pragma unroll
     for (int u = 0; u < BATCH; ++u) {
@@ -286,9 +303,27 @@ kvtrim_status launch_cmp_copy(kvtrim_ctx* ctx, const CacheView& src, const uint8
         ProfScope prof(ctx, K_CMP_COPY, st);
         const dim3 grid((unsigned)max_chunks), block(CMP_THREADS);
         if (sh.head_dim == 128)
-            hipLaunchKernelGGL(k_cmp_copy<128>, grid, block, 0, st, src, keep, dst, sh, ws);
+            hipLaunchKernelGGL((k_cmp_copy<128, false>), grid, block, 0, st, src, keep, dst, sh, ws, nullptr, nullptr, 0, nullptr);
         else
-            hipLaunchKernelGGL(k_cmp_copy<64>, grid, block, 0, st, src, keep, dst, sh, ws);
+            hipLaunchKernelGGL((k_cmp_copy<64, false>), grid, block, 0, st, src, keep, dst, sh, ws, nullptr, nullptr, 0, nullptr);
+    }
+    KVTRIM_HIP(ctx, hipGetLastError());
+    return KVTRIM_OK;
+}
+
+kvtrim_status launch_cmp_copy_new(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const CacheViewMut& dst,
+                                  const uint16_t* k_new, const uint16_t* v_new, int32_t n_new, const int32_t* old_len,
+                                  hipStream_t st) {
+    const Shape& sh = ctx->shape;
+    const Workspace& ws = ctx->ws;
+    const int64_t max_chunks = src.cap / CMP_CHUNK + sh.nseg;
+    if (max_chunks > 0) {
+        ProfScope prof(ctx, K_CMP_COPY, st);
+        const dim3 grid((unsigned)max_chunks), block(CMP_THREADS);
+        if (sh.head_dim == 128)
+            hipLaunchKernelGGL((k_cmp_copy<128, true>), grid, block, 0, st, src, keep, dst, sh, ws, k_new, v_new, n_new, old_len);
+        else
+            hipLaunchKernelGGL((k_cmp_copy<64, true>), grid, block, 0, st, src, keep, dst, sh, ws, k_new, v_new, n_new, old_len);
     }
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;

@@ -86,17 +86,21 @@ __global__ __launch_bounds__(256) void k_append(CacheViewMut c, const uint16_t* 
                                                 const float* __restrict__ lb_new,
                                                 const float* __restrict__ lt_new,
                                                 const int32_t* __restrict__ pos_new, int n_new, int nseg,
-                                                int head_dim, int32_t* err) {
+                                                int head_dim, bool copy_rows, int32_t* __restrict__ old_len_out,
+                                                int32_t* err) {
     __shared__ int s_cnt;
     const int seg = blockIdx.x;
-    if (threadIdx.x == 0) s_cnt = n_new;
+    const int len = c.seg_len[seg];
+    if (threadIdx.x == 0) {
+        s_cnt = n_new;
+        if (old_len_out) old_len_out[seg] = len;                  // whatever happens below: the entries before `len` are the old ones
+    }
     __syncthreads();
     for (int i = threadIdx.x; i < n_new; i += blockDim.x)
         if (pos_new[(int64_t)seg * n_new + i] < 0) atomicMin(&s_cnt, i);
     __syncthreads();
     const int cnt = s_cnt;                                        // rows before the first padding row
     if (cnt == 0) return;
-    const int len = c.seg_len[seg];
     const int64_t start = c.seg_start[seg];
     const int64_t limit = (seg + 1 < nseg) ? c.seg_start[seg + 1] : c.cap;
     if (len < 0 || start < 0 || limit > c.cap || start + len + cnt > limit) {
@@ -108,9 +112,11 @@ __global__ __launch_bounds__(256) void k_append(CacheViewMut c, const uint16_t* 
     const uint4* vs = reinterpret_cast<const uint4*>(v_new) + (int64_t)seg * n_new * vec_per_row;
     uint4* kd = reinterpret_cast<uint4*>(c.k) + (start + len) * vec_per_row;
     uint4* vd = reinterpret_cast<uint4*>(c.v) + (start + len) * vec_per_row;
-    for (int i = threadIdx.x; i < cnt * vec_per_row; i += blockDim.x) {
-        kd[i] = ks[i];
-        vd[i] = vs[i];
+    if (copy_rows) {
+        for (int i = threadIdx.x; i < cnt * vec_per_row; i += blockDim.x) {
+            kd[i] = ks[i];
+            vd[i] = vs[i];
+        }
     }
     for (int i = threadIdx.x; i < cnt; i += blockDim.x) {
         c.log_beta[start + len + i] = lb_new[(int64_t)seg * n_new + i];
@@ -123,11 +129,11 @@ __global__ __launch_bounds__(256) void k_append(CacheViewMut c, const uint16_t* 
 
 kvtrim_status launch_append(kvtrim_ctx* ctx, const CacheViewMut& c, const uint16_t* k_new, const uint16_t* v_new,
                             const float* lb_new, const float* lt_new, const int32_t* pos_new, int32_t n_new,
-                            hipStream_t st) {
+                            bool copy_rows, int32_t* old_len_out, hipStream_t st) {
     const Shape& sh = ctx->shape;
     ProfScope prof(ctx, K_APPEND, st);
     hipLaunchKernelGGL(k_append, dim3(sh.nseg), dim3(256), 0, st, c, k_new, v_new, lb_new, lt_new, pos_new, n_new,
-                       sh.nseg, sh.head_dim, ctx->ws.err);
+                       sh.nseg, sh.head_dim, copy_rows, old_len_out, ctx->ws.err);
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;
 }

@@ -81,6 +81,7 @@ static Layout layout_of(const kvtrim_config* c) {
     l.off[19] = bump(cur, (size_t)nseg * sizeof(int64_t));                     // pg_seg_start
     l.off[20] = bump(cur, (size_t)nseg * sizeof(int32_t));                     // pg_seg_len
     l.off[21] = bump(cur, (size_t)c->n_seq * sizeof(uint32_t));                // seq_done
+    l.off[22] = bump(cur, (size_t)nseg * sizeof(int32_t));                     // chunk_old_len
     l.total = (cur + 255) & ~(size_t)255;
     return l;
 }
@@ -193,6 +194,7 @@ kvtrim_status kvtrim_create(kvtrim_ctx** out, const kvtrim_config* cfg) {
     w.pg_seg_start = (int64_t*)(b + l.off[19]);
     w.pg_seg_len = (int32_t*)(b + l.off[20]);
     w.seq_done = (uint32_t*)(b + l.off[21]);
+    w.chunk_old_len = (int32_t*)(b + l.off[22]);
     w.max_sel_chunks = l.max_sel_chunks;
     w.max_cmp_chunks = l.max_cmp_chunks;
     w.max_att_chunks = l.max_att_chunks;
@@ -391,7 +393,42 @@ kvtrim_status kvtrim_append(kvtrim_ctx* ctx, kvtrim_cache* c, const void* k_new,
     if ((c->log_tail == nullptr) != (log_tail_new == nullptr))
         return invalid(ctx, "log_tail_new is required exactly when the cache carries log_tail");
     return launch_append(ctx, view_mut_of(c), (const uint16_t*)k_new, (const uint16_t*)v_new, log_beta_new,
-                         log_tail_new, pos_new, n_new, (hipStream_t)hip_stream);
+                         log_tail_new, pos_new, n_new, true, nullptr, (hipStream_t)hip_stream);
+}
+
+kvtrim_status kvtrim_append_compact(kvtrim_ctx* ctx, kvtrim_cache* src, const void* k_new, const void* v_new,
+                                    const float* log_beta_new, const float* log_tail_new, const int32_t* pos_new,
+                                    int32_t n_new, const int32_t* now, const int64_t* budget, float* score_out,
+                                    uint8_t* keep_out, int32_t* kept_out, uint32_t* thr_key_out, kvtrim_cache* dst,
+                                    int32_t reserve, void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    if (const char* p = cache_problem(ctx, src, true)) return invalid(ctx, p);
+    if (const char* p = cache_problem(ctx, dst, true)) return invalid(ctx, p);
+    if (!k_new || !v_new || !log_beta_new || !pos_new) return invalid(ctx, "a new-token pointer is NULL");
+    if ((((uintptr_t)k_new) | ((uintptr_t)v_new)) & 15) return invalid(ctx, "k_new / v_new not 16-byte aligned");
+    if (n_new < 1) return invalid(ctx, "n_new < 1");
+    if ((src->log_tail == nullptr) != (log_tail_new == nullptr))
+        return invalid(ctx, "log_tail_new is required exactly when the cache carries log_tail");
+    if (!now || !budget || !score_out || !keep_out || !kept_out)
+        return invalid(ctx, "now / budget / score_out / keep_out / kept_out is NULL");
+    if (reserve < 0) return invalid(ctx, "reserve < 0");
+    if (src->k == dst->k || src->v == dst->v || src->log_beta == dst->log_beta || src->pos == dst->pos ||
+        src->seg_start == dst->seg_start || src->seg_len == dst->seg_len)
+        return invalid(ctx, "src and dst share a buffer");
+    if ((src->log_tail == nullptr) != (dst->log_tail == nullptr) || (src->log_tail && src->log_tail == dst->log_tail))
+        return invalid(ctx, "log_tail must be set in both caches or in neither, and not shared");
+    hipStream_t st = (hipStream_t)hip_stream;
+    kvtrim_status rc = launch_append(ctx, view_mut_of(src), (const uint16_t*)k_new, (const uint16_t*)v_new, log_beta_new,
+                                     log_tail_new, pos_new, n_new, false, ctx->ws.chunk_old_len, st);
+    if (rc != KVTRIM_OK) return rc;
+    const CacheView sv = view_of(src);
+    rc = launch_score(ctx, sv, now, score_out, st);
+    if (rc != KVTRIM_OK) return rc;
+    rc = launch_select(ctx, sv, score_out, budget, keep_out, kept_out, thr_key_out, st);
+    if (rc != KVTRIM_OK) return rc;
+    launch_cmp_scan(ctx, sv, keep_out, kept_out, view_mut_of(dst), reserve, st);
+    return launch_cmp_copy_new(ctx, sv, keep_out, view_mut_of(dst), (const uint16_t*)k_new, (const uint16_t*)v_new, n_new,
+                               ctx->ws.chunk_old_len, st);
 }
 
 }  // extern "C"

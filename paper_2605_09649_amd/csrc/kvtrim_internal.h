@@ -93,6 +93,7 @@ struct Workspace {
     int32_t* pg_seg_len;         // [nseg]
     uint32_t* hist;              // [3][HIST_REPLICAS][n_seq][RADIX_BINS]
     SelState* sel;               // [4][n_seq]: final state; state after the plan, after pass 0, after pass 1
+    int32_t* chunk_old_len;      // [nseg] kvtrim_append_compact: segment lengths before the chunk was appended
     uint32_t* seq_done;          // [n_seq] blocks of the last histogram pass that have added their counts for the sequence
     uint32_t* done;              // [DONE_WORDS] "last block" counters: per pass one top-level and 16 group counters
     int32_t* chunk_eq;           // [max_sel_chunks] entries equal to the threshold
@@ -171,9 +172,16 @@ kvtrim_status launch_compact_attn(kvtrim_ctx*, const CacheView& src, const uint8
                                   const CacheViewMut& dst, int32_t reserve, const uint16_t* q,
                                   int32_t layer_begin, int32_t layer_end, float scale, float* out, float* lse,
                                   hipStream_t);
+// copy_rows = false: only the metadata of the new tokens enters the cache (their K/V rows stay with the caller);
+// old_len_out (or NULL) gets every segment's length before the call.
 kvtrim_status launch_append(kvtrim_ctx*, const CacheViewMut&, const uint16_t* k_new, const uint16_t* v_new,
                             const float* lb_new, const float* lt_new, const int32_t* pos_new, int32_t n_new,
-                            hipStream_t);
+                            bool copy_rows, int32_t* old_len_out, hipStream_t);
+// The row mover for a source whose entries from old_len[seg] on have their K/V rows in k_new / v_new
+// ([nseg][n_new][head_dim]) instead of in src (the tables of k_cmp_scan must be in the workspace).
+kvtrim_status launch_cmp_copy_new(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const CacheViewMut& dst,
+                                  const uint16_t* k_new, const uint16_t* v_new, int32_t n_new, const int32_t* old_len,
+                                  hipStream_t);
 
 kvtrim_status hip_fail(kvtrim_ctx* ctx, hipError_t e, const char* what);
 

@@ -138,11 +138,13 @@ def run_steps_both(w, steps, budget, device="cuda:0", reserve=1, cache_dict=None
     return results
 
 
-def run_multiturn_both(w, lengths, chunk, decode_per_turn, budget, device="cuda:0", turns=4, fused=True):
+def run_multiturn_both(w, lengths, chunk, decode_per_turn, budget, device="cuda:0", turns=4, fused=True,
+                       one_call_chunks=False):
     """The chunked multi-turn flow: every sequence's tokens are split into `turns` turns; a turn appends its tokens
     in chunks of `chunk` (sequences run out at different times: their rows are padded with negative positions) and
     after every chunk the cache is rescored, selected and compacted (no attention); then `decode_per_turn` tokens
-    are decoded with full steps.  Both sides start from empty caches.  Returns one dict of findings per call group."""
+    are decoded with full steps.  Both sides start from empty caches.  Returns one dict of findings per call group.
+    one_call_chunks: the GPU side runs a chunk through kvtrim_append_compact instead of the four calls."""
     per_seq = w.n_layers * w.n_kv_heads
     S, nseg, D = w.n_seq, w.nseg, w.head_dim
     reserve = chunk                                                # room behind every segment for the next chunk
@@ -177,12 +179,20 @@ def run_multiturn_both(w, lengths, chunk, decode_per_turn, budget, device="cuda:
         hc_next = oracle.compact(hc, k_ref, cap, reserve)
         # ---- GPU
         d = {k: v.to(device) for k, v in inp.items()}
-        kv.kvtrim_append(ctx, cur, d["k_new"], d["v_new"], d["log_beta_new"], torch.from_numpy(pos_new).to(device), n_new)
-        kv.kvtrim_score(ctx, cur, torch.from_numpy(now).to(device), score)
-        kv.kvtrim_select_global(ctx, cur, score, budget_dev, keep, kept, thr)
         dst = caches[flip]
         res = {"what": label}
-        if attend_q is None:
+        one_call = attend_q is None and one_call_chunks
+        if one_call:
+            kv.kvtrim_append_compact(ctx, cur, d["k_new"], d["v_new"], d["log_beta_new"], torch.from_numpy(pos_new).to(device),
+                                     n_new, torch.from_numpy(now).to(device), budget_dev, score, keep, kept, dst, reserve,
+                                     thr_key_out=thr)
+        else:
+            kv.kvtrim_append(ctx, cur, d["k_new"], d["v_new"], d["log_beta_new"], torch.from_numpy(pos_new).to(device), n_new)
+            kv.kvtrim_score(ctx, cur, torch.from_numpy(now).to(device), score)
+            kv.kvtrim_select_global(ctx, cur, score, budget_dev, keep, kept, thr)
+        if one_call:
+            pass
+        elif attend_q is None:
             kv.kvtrim_compact(ctx, cur, keep, kept, dst, reserve)
         elif fused:
             kv.kvtrim_compact_attn(ctx, cur, keep, kept, dst, reserve, attend_q.to(device), 0, w.n_layers, scale, out, lse)

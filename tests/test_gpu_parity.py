@@ -80,6 +80,48 @@ def test_multi_turn_chunked_prefill_then_decode(fused):
             assert r["attn_err"] <= ATTN_TOL and r["lse_err"] <= 2e-3, r
 
 
+@pytest.mark.parametrize("D", [64, 128])
+def test_multi_turn_chunks_in_one_call(D):
+    # the same flow with every chunk step done by kvtrim_append_compact (metadata appended, rows moved once, from
+    # the caller's buffers to the compacted cache): scores, mask, counts, threshold and cache as the oracle's four stages
+    w = wl(3, 2, 2, 2, D)
+    res = run_multiturn_both(w, [700, 180, 411], chunk=64, decode_per_turn=2, budget=[160, 10 ** 6, 96], device=DEV,
+                             one_call_chunks=True)
+    assert sum("chunk" in r["what"] for r in res) > 10
+    for r in res:
+        assert r["status"] == 0 and r["score_equal"] and r["keep_equal"] and r["cache_equal"], r
+        if "attn_err" in r:
+            assert r["attn_err"] <= ATTN_TOL and r["lse_err"] <= 2e-3, r
+
+
+def test_multi_turn_chunks_in_one_call_sixteen_sequences():
+    w = ki.workload("multiturn", prefill=1024)                   # S16 L32 Hkv8 Hq32 D128, lengths in [64, 1024]
+    res = run_multiturn_both(w, list(w.prefill), chunk=256, decode_per_turn=1, budget=[96 * 32 * 8] * 16, device=DEV,
+                             turns=2, one_call_chunks=True)
+    for r in res:
+        assert r["status"] == 0 and r["score_equal"] and r["keep_equal"] and r["cache_equal"], r
+
+
+def test_append_compact_argument_checks():
+    w = wl(1, 1, 1, 1, 64)
+    nseg, cap = 1, 64
+    ctx = kv.Context(1, 1, 1, 1, 64, cap)
+    a, b = kv.Cache.empty(nseg, 64, cap, DEV), kv.Cache.empty(nseg, 64, cap, DEV)
+    t = lambda *shape, dt=torch.float32: torch.zeros(*shape, dtype=dt, device=DEV)
+    k_new, lb, pos = t(1, 4, 64, dt=torch.bfloat16), t(1, 4), t(1, 4, dt=torch.int32)
+    now, budget = t(1, dt=torch.int32), t(1, dt=torch.int64)
+    score, keep, kept = t(cap), t(cap, dt=torch.uint8), t(nseg, dt=torch.int32)
+    with pytest.raises(kv.KvtrimError):                           # source and destination share buffers
+        kv.kvtrim_append_compact(ctx, a, k_new, k_new, lb, pos, 4, now, budget, score, keep, kept, a, 0)
+    with pytest.raises(kv.KvtrimError):                           # no tokens
+        kv.kvtrim_append_compact(ctx, a, k_new, k_new, lb, pos, 0, now, budget, score, keep, kept, b, 0)
+    with pytest.raises(kv.KvtrimError):                           # a missing output
+        kv.kvtrim_append_compact(ctx, a, k_new, k_new, lb, pos, 4, now, budget, None, keep, kept, b, 0)
+    with pytest.raises(kv.KvtrimError):                           # the tail constant without a cache that carries it
+        kv.kvtrim_append_compact(ctx, a, k_new, k_new, lb, pos, 4, now, budget, score, keep, kept, b, 0, log_tail_new=lb)
+    assert kv.kvtrim_poll_error(ctx) == 0
+
+
 def test_multi_turn_chunked_sixteen_sequences():
     w = ki.workload("multiturn", prefill=1024)                   # S16 L32 Hkv8 Hq32 D128, lengths in [64, 1024]
     per_head = 96
