@@ -102,6 +102,55 @@ def test_multi_turn_chunks_in_one_call_sixteen_sequences():
         assert r["status"] == 0 and r["score_equal"] and r["keep_equal"] and r["cache_equal"], r
 
 
+@pytest.mark.parametrize("horizon", [1, 2, 0])
+def test_append_compact_on_a_ragged_cache(horizon):
+    # one call on a cache with gapped positions and an empty segment: sequence 0 brings a full chunk, sequence 1 a
+    # ragged one (padding rows behind its 11 tokens); with a lookahead horizon the new tokens bring their tail constant
+    w = wl(2, 2, 3, 2, 128)
+    rng = np.random.default_rng(5 + horizon)
+    seg_len = rng.integers(1, 300, w.nseg)
+    seg_len[3] = 0
+    n_new, per_seq = 37, w.n_layers * w.n_kv_heads
+    c, now = ki.ragged_cache(w, seg_len, reserve=n_new, salt=9)
+    c = ki.with_horizon(c, horizon)
+    inp = ki.chunk_inputs(w, n_new, "cpu", 3)
+    lt_new = None if horizon == 1 else ki.log_tail_of(inp["log_beta_new"], horizon)
+    take = [n_new, 11]
+    pos_new = np.full((w.nseg, n_new), -1, np.int32)
+    for s in range(2):
+        pos_new[s * per_seq:(s + 1) * per_seq, :take[s]] = int(now[s]) + np.arange(take[s])
+    now_after = (now.numpy() + np.array(take) - 1).astype(np.int32)
+    n_seq_entries = [int(seg_len[s * per_seq:(s + 1) * per_seq].sum()) + take[s] * per_seq for s in range(2)]
+    budget = np.array([n_seq_entries[0] // 2, n_seq_entries[1] - 5], np.int64)
+    cap = c["cap"]
+    # ---- oracle: the four stages
+    hc = host_cache(w, c)
+    oracle.append(hc, bf16_bits(inp["k_new"]), bf16_bits(inp["v_new"]), inp["log_beta_new"].numpy(), pos_new,
+                  log_tail_new=None if lt_new is None else lt_new.numpy())
+    s_ref = oracle.score(hc, now_after)
+    k_ref, kept_ref, thr_ref = oracle.select(hc, s_ref, budget)
+    hc_next = oracle.compact(hc, k_ref, cap, 1)
+    # ---- GPU: one call
+    ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, cap)
+    src = kv.Cache.from_dict(c, DEV)
+    dst = kv.Cache.empty(w.nseg, w.head_dim, cap, DEV, with_tail=horizon != 1)
+    score = torch.zeros(cap, dtype=torch.float32, device=DEV)
+    keep = torch.zeros(cap, dtype=torch.uint8, device=DEV)
+    kept = torch.zeros(w.nseg, dtype=torch.int32, device=DEV)
+    thr = torch.zeros(w.n_seq, dtype=torch.int32, device=DEV)
+    kv.kvtrim_append_compact(ctx, src, inp["k_new"].to(DEV), inp["v_new"].to(DEV), inp["log_beta_new"].to(DEV),
+                             torch.from_numpy(pos_new).to(DEV), n_new, torch.from_numpy(now_after).to(DEV),
+                             torch.from_numpy(budget).to(DEV), score, keep, kept, dst, 1, thr_key_out=thr,
+                             log_tail_new=None if lt_new is None else lt_new.to(DEV))
+    assert kv.kvtrim_poll_error(ctx) == 0
+    live = live_mask(hc)
+    assert np.array_equal(score.cpu().numpy()[live].view(np.uint32), s_ref[live].view(np.uint32))
+    assert np.array_equal(keep.cpu().numpy()[live], k_ref[live]) and np.array_equal(kept.cpu().numpy(), kept_ref)
+    assert np.array_equal(thr.cpu().numpy().view(np.uint32), thr_ref)
+    assert compare_caches(device_cache_to_host(w, dst), hc_next)
+    assert int(kept_ref.sum()) == int(budget.sum())
+
+
 def test_append_compact_argument_checks():
     w = wl(1, 1, 1, 1, 64)
     nseg, cap = 1, 64
