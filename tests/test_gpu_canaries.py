@@ -152,3 +152,40 @@ def test_gate_forward_stays_inside_scratch_and_outputs(L, H, d_model, d_g, d_p, 
     torch.cuda.synchronize()
     assert gd.intact()
     assert bool(((lb2 - lb).abs() <= 2e-4 * lb.abs()).all())
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_chunk_steps_in_one_call_stay_inside_the_buffers(D):
+    # kvtrim_append_compact over three chunks (the last one ragged): the source gets metadata only, the destination
+    # the surviving rows; the guards of both caches, of the new-token buffers and of the outputs stay untouched
+    w = ki.Workload("c", 0, 2, 2, 3, 6, D, (0, 0), (0, 0), 1, 3.0, 1.5)
+    n_new, per_seq = 50, w.n_layers * w.n_kv_heads
+    budget_per_seq = 40 * per_seq
+    cap = 2 * budget_per_seq + w.nseg * n_new + 8
+    gd = Guarded()
+    caches = [guarded_cache(gd, w.nseg, D, cap) for _ in range(2)]
+    caches[0].seg_start.copy_(torch.arange(w.nseg, dtype=torch.int64) * n_new)
+    ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, D, cap)
+    score, keep = gd.make((cap,), torch.float32), gd.make((cap,), torch.uint8)
+    kept, thr = gd.make((w.nseg,), torch.int32), gd.make((w.n_seq,), torch.int32)
+    budget = torch.full((w.n_seq,), budget_per_seq, dtype=torch.int64, device=DEV)
+    k_new, v_new = gd.make((w.nseg, n_new, D), torch.bfloat16), gd.make((w.nseg, n_new, D), torch.bfloat16)
+    lb_new, pos_new = gd.make((w.nseg, n_new), torch.float32), gd.make((w.nseg, n_new), torch.int32)
+    next_pos = np.zeros(w.n_seq, np.int64)
+    cur = 0
+    for step, take in enumerate([(50, 50), (50, 50), (50, 7)]):
+        inp = ki.chunk_inputs(w, n_new, DEV, step)
+        k_new.copy_(inp["k_new"]); v_new.copy_(inp["v_new"]); lb_new.copy_(inp["log_beta_new"])
+        pn = np.full((w.nseg, n_new), -1, np.int32)
+        for s in range(w.n_seq):
+            pn[s * per_seq:(s + 1) * per_seq, :take[s]] = next_pos[s] + np.arange(take[s])
+        next_pos += np.array(take)
+        pos_new.copy_(torch.from_numpy(pn))
+        now = torch.from_numpy((next_pos - 1).astype(np.int32)).to(DEV)
+        kv.kvtrim_append_compact(ctx, caches[cur], k_new, v_new, lb_new, pos_new, n_new, now, budget, score, keep, kept,
+                                 caches[cur ^ 1], n_new, thr_key_out=thr)
+        assert kv.kvtrim_poll_error(ctx) == 0, step
+        assert gd.intact(), step
+        cur ^= 1
+    live = caches[cur].seg_len.cpu().numpy().reshape(w.n_seq, per_seq).sum(1)
+    assert list(live) == [budget_per_seq, budget_per_seq]          # 150 and 107 tokens per list came in, 40 per list stay
