@@ -27,6 +27,19 @@ MEASURED_TRAFFIC = {("long", "k_cmp_attn"): 1.1011e9 + 1.1262e9, ("long", "k_cmp
                     ("long-paged", "k_att_partial"): 1.0942e9 + 8.8e6, ("gate-1", "k_gate_hidden"): 136.5e6 + 65.5e3}
 
 
+def rows_moved_in_place(cache, keep):
+    """Rows an in-place stable compaction has to write: the survivors behind the first evicted entry of their segment."""
+    k = keep.cpu().numpy()
+    st, ln = cache.seg_start.cpu().numpy(), cache.seg_len.cpu().numpy()
+    moved = 0
+    for g in range(len(st)):
+        kk = k[st[g]:st[g] + ln[g]]
+        ev = (kk == 0).nonzero()[0]
+        if len(ev):
+            moved += int(kk[ev[0]:].sum())
+    return moved
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -310,6 +323,9 @@ def main():
     ap.add_argument("--chunk", type=int, default=0, metavar="N_TOK",
                     help="time the chunked-prefill step of the multi-turn workload instead of decode steps: N_TOK new "
                          "tokens per segment, then rescore, select, compact (the paper-shaped chunk is 4096)")
+    ap.add_argument("--inplace", type=int, default=0, metavar="ROOM",
+                    help="compact inside the cache (kvtrim_compact_attn_inplace: rows move only behind an eviction) with ROOM "
+                         "free slots behind every segment; every ROOM-th step is an out-of-place step that evens the room out")
     ap.add_argument("--one-call", action="store_true",
                     help="with --chunk (ragged layout): the chunk step through kvtrim_append_compact, which moves the new rows "
                          "once, from the caller's buffers to the compacted cache")
@@ -330,6 +346,8 @@ def main():
         return bench_gate(args)
     if args.paged and args.unfused:
         ap.error("--paged and --unfused exclude each other")
+    if args.inplace and (args.paged or args.unfused or args.inplace < 2):
+        ap.error("--inplace takes a room of at least 2 slots and excludes --paged and --unfused")
     if args.defrag_every and not args.paged:
         ap.error("--defrag-every needs --paged")
     if args.gpus != 1:
@@ -344,10 +362,10 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     w = ki.workload(args.workload, prefill=args.prefill)
-    reserve = 1
+    reserve = args.inplace if args.inplace else 1                 # free slots behind every segment after an out-of-place step
     K, W = args.steps, max(args.warmup, 1)
     G_STEPS = 20 if args.graph else 0         # eager, profiled steps before a captured region
-    n_steps = K + W + G_STEPS + CPU_STEPS     # + the extra steps that are replayed on the CPU oracle
+    n_steps = K + W + G_STEPS + CPU_STEPS + 1 # + the extra steps that are replayed on the CPU oracle, + one that is looked at
 
     t0 = time.time()
     pre = ki.with_horizon(ki.prefill_cache(w, reserve=reserve, device=dev), args.horizon)
@@ -415,6 +433,10 @@ def main():
             state["src"] = None
             return
         dst = spare[state["flip"]]
+        if args.inplace and s > 0 and s % args.inplace:
+            # the other cache lends its arrays as parking space; the segments stay where they are
+            kv.kvtrim_compact_attn_inplace(ctx, cur, keep, kept, dst, inp["q"], 0, w.n_layers, scale, out, lse)
+            return
         if args.unfused:
             kv.kvtrim_compact(ctx, cur, keep, kept, dst, reserve)
             kv.kvtrim_decode_attn(ctx, dst, inp["q"], 0, w.n_layers, scale, out, lse)
@@ -480,6 +502,7 @@ def main():
         for name, (ms, n) in sorted(prof.items(), key=lambda kvp: -kvp[1][0]):
             log(f"[bench]   {name:16s} {ms / n * 1e3:8.1f} us x {n}")
     ms_per_step = (t_end - t_begin) * 1e3 / K
+    inplace_info = None
     alg = algorithmic_bytes(w, n_cand, n_ret, args.horizon)
     alg_total = sum(alg.values())
     stage_model_bytes = None
@@ -501,6 +524,36 @@ def main():
         dom = "k_cmp_attn"
         dom_bytes = alg["compact"] + n_cand + 6 * w.head_dim * w.n_seq * w.n_layers * w.n_q_heads
         stage_model_bytes = alg["compact"] + alg["attend"]
+        if args.inplace:
+            # In place every retained entry is read once (4D + 8 B) and only the rows behind an eviction are written.
+            # How many those are depends on the data: they are counted on one more step after the timed region.
+            # One launch in ROOM is out of place.
+            s_extra = W + G_STEPS + K                              # the step right after the timed region
+            if s_extra % args.inplace == 0:
+                step(s_extra)                                      # (an out-of-place step falls here: look at the next one)
+                s_extra = None
+            moved = None
+            if s_extra is not None:
+                inp, cur = inputs[s_extra], state["src"]
+                kv.kvtrim_append(ctx, cur, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos_news[s_extra], 1,
+                                 log_tail_new=inp.get("log_tail_new"))
+                kv.kvtrim_score(ctx, cur, nows[s_extra], score)
+                kv.kvtrim_select_global(ctx, cur, score, budget, keep, kept, thr)
+                torch.cuda.synchronize()
+                moved = rows_moved_in_place(cur, keep)
+                kv.kvtrim_compact_attn_inplace(ctx, cur, keep, kept, spare[state["flip"]], inp["q"], 0, w.n_layers, scale, out, lse)
+                torch.cuda.synchronize()
+                log(f"[bench] in place: {moved} of {n_ret} retained rows ({100.0 * moved / n_ret:.1f} %) lie behind an eviction "
+                    f"and are written; the others are only read")
+            row_bytes = alg["compact"] // (2 * n_ret)
+            inplace_bytes = (alg["compact"] // 2 + row_bytes * (moved or 0) +
+                             6 * w.head_dim * w.n_seq * w.n_layers * w.n_q_heads)
+            dom_bytes = ((args.inplace - 1) * inplace_bytes + dom_bytes) // args.inplace
+            stage_model_bytes = None
+            alg = {"score": alg["score"], "select": alg["select"],
+                   "compact+attend (in place: every retained row read, the rows behind an eviction written)": dom_bytes}
+            alg_total = sum(alg.values())
+            inplace_info = {"room": args.inplace, "rows_written_sampled": moved, "rows_retained": n_ret}
     if dom not in prof and "k_att_fused" in prof:   # large groups of query heads: the loop-shaped fused kernel, same bytes
         dom = "k_att_fused"
     if dom not in prof:                       # the cache is too large for the fused kernel: the library ran the two stages
@@ -537,6 +590,8 @@ def main():
             "stages": ("paged_append, paged_score, paged_select, paged_evict, paged_attn (paged layout: no K/V moved; "
                        "five C-ABI calls per step)" if args.paged else
                        "append, score, select_global, compact, decode_attn (five C-ABI calls per step)" if args.unfused else
+                       f"append, score, select_global, compact_attn_inplace (stages 3+4 fused inside the cache, {args.inplace} free "
+                       f"slots per segment; every {args.inplace}th step is an out-of-place compact_attn)" if args.inplace else
                        "append, score, select_global, compact_attn (stages 3+4 fused; four C-ABI calls per step)"),
             "first_step_ms": first_ms,
             "launch": "one HIP graph holding the K timed steps, replayed once" if args.graph else "eager launches",
@@ -546,13 +601,15 @@ def main():
                        "bytes_by_stage": alg},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC.get((w.name + ("-paged" if args.paged else ""), dom)),
+                     "traffic": None if args.inplace else MEASURED_TRAFFIC.get((w.name + ("-paged" if args.paged else ""), dom)),
                      "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_avg_ms, "launches": dom_n,
                      "stage_model_bytes_per_launch": stage_model_bytes,
                      "stage_model_achieved": (stage_model_bytes / (dom_avg_ms * 1e-3) / 1e9) if stage_model_bytes else None,
                      "second_kernel": second},
     }
 
+    if inplace_info:
+        result["config"]["in_place"] = inplace_info
     if args.paged:
         result["config"]["pages"] = {"page_size": kv.PAGE_SIZE, "n_pages": pc.n_pages,
                                      "in_use_after_timed_region": int(pc.seg_pages.sum().item())}
@@ -562,7 +619,7 @@ def main():
     # GPU's results of those steps are checked against it (selection/compaction bit-exact, attention 5e-3)
     if not args.no_cpu_baseline:
         import oracle
-        from harness import attn_error, compare_caches, device_cache_to_host
+        from harness import attn_error, compare_cache_contents, compare_caches, device_cache_to_host
         from helpers import bf16_bits
         if args.paged:                          # the pages as the oracle's ragged cache: each segment in position order
             from paged_harness import PagedHost
@@ -573,7 +630,8 @@ def main():
             hc = device_cache_to_host(w, state["src"])
         budget_np = np.array(list(w.budget), np.int64)
         cpu_s, ok_sel, err = 0.0, True, 0.0
-        for s in range(W + G_STEPS + K, W + G_STEPS + K + CPU_STEPS):
+        first_cpu = W + G_STEPS + K + (1 if args.inplace else 0)   # (in place: one step was spent counting moved rows)
+        for s in range(first_cpu, first_cpu + CPU_STEPS):
             inp = {k: v.cpu() for k, v in inputs[s].items()}
             now = now0 + s + 1
             pos_new = np.repeat(now, per_seq).astype(np.int32)
@@ -594,6 +652,8 @@ def main():
         if args.paged:
             ph = PagedHost(pc)
             ok_cache = ph.structure_problems() == [] and ph.equals(hc)
+        elif args.inplace:                      # the segments keep their starts: contents are compared segment by segment
+            ok_cache = compare_cache_contents(device_cache_to_host(w, state["src"]), hc)
         else:
             ok_cache = compare_caches(device_cache_to_host(w, state["src"]), hc)
         log(f"[bench] {CPU_STEPS} oracle steps on the host: {cpu_s:.2f} s; GPU vs oracle on those steps: kept equal={ok_sel}, "

@@ -185,6 +185,27 @@ kvtrim_status kvtrim_compact_attn(kvtrim_ctx *ctx, const kvtrim_cache *src, cons
                                   int32_t layer_begin, int32_t layer_end, float softmax_scale, float *out,
                                   float *lse, void *hip_stream);
 
+/* Stages 3 + 4 fused, compacting INSIDE the cache: every segment keeps its seg_start, its
+ * survivors (keep, kept as produced by kvtrim_select_global for this cache) close up to the
+ * front of its region in their order, seg_len becomes kept, and out / lse are the attention
+ * over the survivors, as kvtrim_compact_attn gives them.  A row moves only if an entry before it in
+ * its segment was evicted, and a row that stays is not written: in a decode step, where one
+ * entry in thousands goes, most of the cache is read once for the attention and not written.
+ * Segment contents afterwards equal those kvtrim_compact produces; the free slots behind a
+ * segment (its room for later kvtrim_append calls) grow and shrink with its length, so a caller
+ * runs an out-of-place step (kvtrim_compact_attn with a `reserve`) now and then to even them
+ * out - kvtrim_append reports KVTRIM_ECAP when a segment has run out.
+ * spare: a second cache structure whose k, v, log_beta, pos (and log_tail if c has one)
+ * arrays hold at least c->cap_entries entries and are distinct from c's; the call parks a few
+ * rows there while it runs (those that move into a region another thread block may still be
+ * reading); its contents afterwards are unspecified, its segment tables are not touched.
+ * Served for up to 6 query heads per KV head and caches of at most 67 M entries
+ * (KVTRIM_EINVAL otherwise).  Device-side errors: KVTRIM_EMISMATCH, KVTRIM_ELAYOUT. */
+kvtrim_status kvtrim_compact_attn_inplace(kvtrim_ctx *ctx, kvtrim_cache *c, const uint8_t *keep,
+                                          const int32_t *kept, kvtrim_cache *spare, const void *q,
+                                          int32_t layer_begin, int32_t layer_end, float softmax_scale,
+                                          float *out, float *lse, void *hip_stream);
+
 /* Support - new tokens enter the cache (Sec. 3.2: beta is fixed when the token is
  * first cached).  Appends up to n_new entries to every segment, in order, behind its
  * current end and adds their number to seg_len.  k_new, v_new: device bf16
@@ -381,7 +402,7 @@ kvtrim_status kvtrim_gate_forward_prepared(kvtrim_ctx *ctx, const kvtrim_gate *g
  * end waits for `hip_stream` and writes, per kernel id, the summed duration in
  * milliseconds and the number of bracketed launches into host arrays of
  * KVTRIM_N_KERNELS elements.  Do not capture a HIP graph while profiling is on. */
-#define KVTRIM_N_KERNELS 31
+#define KVTRIM_N_KERNELS 32
 #define KVTRIM_PROFILE_MAX_LAUNCHES 4096
 kvtrim_status kvtrim_profile_begin(kvtrim_ctx *ctx, uint32_t kernel_mask);
 kvtrim_status kvtrim_profile_end(kvtrim_ctx *ctx, void *hip_stream, double *ms_sum_host,

@@ -37,9 +37,11 @@ __device__ __forceinline__ void block_sum_n(int64_t (&v)[N], int64_t* lds /* [16
 // With many segments the per-block reduction over all segments below costs more than a launch: one block
 // then scans the segments once and leaves, per segment, the first chunk (ws.cmp_chunk_prefix) and the first
 // destination entry (dst.seg_start) - the two values k_cmp_scan would otherwise derive in every block.
+// inplace: the survivors stay in their segment's own region (dst is the same cache): the segment starts stand as
+// they are and there is no capacity to check.
 __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_prefix(CacheView src, const int32_t* __restrict__ kept,
                                                              CacheViewMut dst, int reserve, int align, Shape sh,
-                                                             Workspace ws) {
+                                                             Workspace ws, int inplace) {
     __shared__ int64_t lds64[17];
     __shared__ int s_bad_layout, s_bad_kept;
     const int tid = threadIdx.x, nseg = sh.nseg;
@@ -63,7 +65,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_prefix(CacheView src, cons
         const int64_t ex_e = block_excl_scan<int64_t>(need, lds64, &tot_e);
         if (i < nseg) {
             ws.cmp_chunk_prefix[i] = (int32_t)min(chunks + ex_c, (int64_t)0x7fffffff);
-            dst.seg_start[i] = entries + ex_e;
+            if (!inplace) dst.seg_start[i] = entries + ex_e;
         }
         chunks += tot_c;
         entries += tot_e;
@@ -71,7 +73,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_prefix(CacheView src, cons
     __syncthreads();
     const bool bad_layout = s_bad_layout || chunks > ws.max_cmp_chunks, bad_kept = s_bad_kept != 0;
     if (tid == 0) {
-        if (bad_layout || bad_kept || entries > dst.cap) {
+        if (bad_layout || bad_kept || (!inplace && entries > dst.cap)) {
             atomicOr(ws.err, bad_layout ? ERR_LAYOUT : (bad_kept ? ERR_MISMATCH : ERR_CAP));
             ws.cmp_chunk_prefix[nseg] = 0;
         } else {
@@ -84,7 +86,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_prefix(CacheView src, cons
 template <bool PRE>
 __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const uint8_t* __restrict__ keep,
                                                            const int32_t* __restrict__ kept, CacheViewMut dst,
-                                                           int reserve, int align, Shape sh, Workspace ws) {
+                                                           int reserve, int align, Shape sh, Workspace ws, int inplace) {
     __shared__ int64_t lds64[17];
     __shared__ int64_t lds_n[16 * 6];
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
@@ -119,7 +121,8 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const 
         dst_before = acc[1];
         const int64_t dst_total = acc[2], chunks_total = acc[3];
         const bool bad_layout = acc[4] != 0 || chunks_total > ws.max_cmp_chunks, bad_kept = acc[5] != 0;
-        if (bad_layout || bad_kept || dst_total > dst.cap) {       // every block takes the same decision
+        if (inplace) dst_before = src.seg_start[g];               // the segment keeps its place
+        if (bad_layout || bad_kept || (!inplace && dst_total > dst.cap)) {   // every block takes the same decision
             if (tid == 0) {
                 atomicOr(ws.err, bad_layout ? ERR_LAYOUT : (bad_kept ? ERR_MISMATCH : ERR_CAP));
                 if (g == 0) ws.cmp_chunk_prefix[nseg] = 0;
@@ -167,8 +170,10 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const 
     }
     if (tid == 0) {
         if (running != kept[g]) atomicOr(ws.err, ERR_MISMATCH);
-        dst.seg_start[g] = dst_before;
-        dst.seg_len[g] = kept[g];
+        if (!inplace) {                                           // (in place the other blocks are still reading the lengths:
+            dst.seg_start[g] = dst_before;                        //  the mover's last kernel commits them)
+            dst.seg_len[g] = kept[g];
+        }
         if (!PRE) {
             ws.cmp_chunk_prefix[g] = cbase;
             if (g == nseg - 1) ws.cmp_chunk_prefix[nseg] = cbase + nch;
@@ -273,12 +278,29 @@ void launch_cmp_scan_aligned(kvtrim_ctx* ctx, const CacheView& src, const uint8_
                              const CacheViewMut& dst, int32_t reserve, int32_t align, hipStream_t st) {
     ProfScope prof(ctx, K_CMP_SCAN, st);
     if (ctx->shape.nseg > 1024) {                                 // see k_cmp_prefix
-        hipLaunchKernelGGL(k_cmp_prefix, dim3(1), dim3(SCAN_THREADS), 0, st, src, kept, dst, reserve, align, ctx->shape, ctx->ws);
+        hipLaunchKernelGGL(k_cmp_prefix, dim3(1), dim3(SCAN_THREADS), 0, st, src, kept, dst, reserve, align, ctx->shape, ctx->ws, 0);
         hipLaunchKernelGGL(k_cmp_scan<true>, dim3(ctx->shape.nseg), dim3(SCAN_THREADS), 0, st, src, keep, kept, dst, reserve,
-                           align, ctx->shape, ctx->ws);
+                           align, ctx->shape, ctx->ws, 0);
     } else {
         hipLaunchKernelGGL(k_cmp_scan<false>, dim3(ctx->shape.nseg), dim3(SCAN_THREADS), 0, st, src, keep, kept, dst, reserve,
-                           align, ctx->shape, ctx->ws);
+                           align, ctx->shape, ctx->ws, 0);
+    }
+}
+
+// The tables for a compaction inside the cache itself: every segment keeps its start, chunk ch's survivors go to
+// ws.cmp_chunk_dst[ch] = seg_start + survivors of the segment's earlier chunks; nothing of the cache is written.
+void launch_cmp_scan_inplace(kvtrim_ctx* ctx, const CacheViewMut& c, const uint8_t* keep, const int32_t* kept, hipStream_t st) {
+    ProfScope prof(ctx, K_CMP_SCAN, st);
+    CacheView src;
+    src.k = c.k; src.v = c.v; src.log_beta = c.log_beta; src.pos = c.pos;
+    src.seg_start = c.seg_start; src.seg_len = c.seg_len; src.cap = c.cap; src.log_tail = c.log_tail;
+    if (ctx->shape.nseg > 1024) {
+        hipLaunchKernelGGL(k_cmp_prefix, dim3(1), dim3(SCAN_THREADS), 0, st, src, kept, c, 0, 1, ctx->shape, ctx->ws, 1);
+        hipLaunchKernelGGL(k_cmp_scan<true>, dim3(ctx->shape.nseg), dim3(SCAN_THREADS), 0, st, src, keep, kept, c, 0, 1,
+                           ctx->shape, ctx->ws, 1);
+    } else {
+        hipLaunchKernelGGL(k_cmp_scan<false>, dim3(ctx->shape.nseg), dim3(SCAN_THREADS), 0, st, src, keep, kept, c, 0, 1,
+                           ctx->shape, ctx->ws, 1);
     }
 }
 

@@ -75,9 +75,16 @@ __device__ __forceinline__ float row16_sum(float x) {
     return x;
 }
 
-template <int D, int G>
+// INPLACE: src and dst are the same cache and every segment keeps its start (tables from launch_cmp_scan_inplace),
+// so survivor r of a chunk moves left by the number of entries evicted before it, or not at all.  A block may
+// overwrite its own chunk's entries once all of its wavefronts hold their rows in registers; the (few) survivors
+// whose destination lies in an earlier chunk's range - which another block may still be reading - go to the same
+// index of `stage` instead, and k_cmp_unstage puts them in place after this kernel has ended.  Rows that do not move
+// are not written at all.
+template <int D, int G, bool INPLACE>
 __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const uint8_t* __restrict__ keep,
-                                                          CacheViewMut dst, const uint16_t* __restrict__ q,
+                                                          CacheViewMut dst, CacheViewMut stage,
+                                                          const uint16_t* __restrict__ q,
                                                           Shape sh, Workspace ws, float scale_log2,
                                                           int layer_begin, int layer_end) {
     typedef Row<D> R;
@@ -106,8 +113,8 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
     const bool full = (dflag & CMP_DST_FULL) != 0;                // uniform over the block
     int cnt = 0;
     float md_lb = 0.f, md_lt = 0.f;
-    int md_pos = 0;
-    const bool md_mine = full && tid < cd.n;
+    int md_pos = 0, md_rank = tid;
+    bool md_mine = full && tid < cd.n;                            // this thread carries an entry's metadata in registers
     if (full) {
         cnt = cd.n;
         if (md_mine) {
@@ -132,12 +139,22 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
         }
         if (flag) {
             list[rank] = tid;
-            dst.log_beta[dbase + rank] = src.log_beta[sbase + tid];
-            if (src.log_tail) dst.log_tail[dbase + rank] = src.log_tail[sbase + tid];
-            dst.pos[dbase + rank] = src.pos[sbase + tid];
+            if (INPLACE) {                                        // written after the whole block has read its entries
+                md_mine = true;
+                md_rank = rank;
+                md_lb = src.log_beta[sbase + tid];
+                if (src.log_tail) md_lt = src.log_tail[sbase + tid];
+                md_pos = src.pos[sbase + tid];
+            } else {
+                dst.log_beta[dbase + rank] = src.log_beta[sbase + tid];
+                if (src.log_tail) dst.log_tail[dbase + rank] = src.log_tail[sbase + tid];
+                dst.pos[dbase + rank] = src.pos[sbase + tid];
+            }
         }
         __syncthreads();
     }
+    // INPLACE: nothing of this chunk moves when it loses nothing and nothing was evicted before it in its segment
+    const bool moves = !INPLACE || !(full && dbase == sbase);     // uniform over the block
 
     const int seg = cd.seg;
     const int seq = seg / sh.segs_per_seq, lh = seg % sh.segs_per_seq;
@@ -156,75 +173,107 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
         for (int e = 0; e < E; ++e) o[g][e] = 0.f;
     }
 
-    if (has_rows) {
-        const vec* sk = reinterpret_cast<const vec*>(src.k);
-        const vec* sv = reinterpret_cast<const vec*>(src.v);
-        vec* dk = reinterpret_cast<vec*>(dst.k);
-        vec* dv = reinterpret_cast<vec*>(dst.v);
-        vec kk[4], vv[4];
+    const vec* sk = reinterpret_cast<const vec*>(src.k);
+    const vec* sv = reinterpret_cast<const vec*>(src.v);
+    // the three steps of a wavefront that has rows: fetch rows and queries, write the rows out, attend
+    auto fetch = [&](vec (&kk)[4], vec (&vv)[4], int (&srow)[4], float (&qf)[G][E]) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int r = min(r0 + u * 4 + sub, cnt - 1);         // clamped: loads stay on live rows
-            const int64_t se = (sbase + (full ? r : list[r])) * VPR + col;
+            srow[u] = full ? r : list[r];                         // the chunk entry the row comes from
+            const int64_t se = (sbase + srow[u]) * VPR + col;
             kk[u] = R::ld(sk + se);
             vv[u] = R::ld(sv + se);
         }
-        float qf[G][E];
         if (attend) {
             const int64_t hq0 = ((int64_t)seq * sh.n_layers + layer) * sh.n_q_heads + (int64_t)head * G;
 #pragma unroll
             for (int g = 0; g < G; ++g) R::unpack(reinterpret_cast<const vec*>(q + (hq0 + g) * D)[col], qf[g]);
         }
+    };
+    auto write_rows = [&](const vec (&kk)[4], const vec (&vv)[4], const int (&srow)[4]) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int r = r0 + u * 4 + sub;
-            if (r < cnt) {
+            if (r < cnt && (!INPLACE || dbase + r != sbase + srow[u])) {   // INPLACE: a row that stays is not written
                 const int64_t de = (dbase + r) * VPR + col;
-                R::st(dk + de, kk[u]);
-                R::st(dv + de, vv[u]);
+                const bool own = !INPLACE || dbase + r >= sbase;  // inside this chunk's own range (or another buffer)
+                R::st(reinterpret_cast<vec*>(own ? dst.k : stage.k) + de, kk[u]);
+                R::st(reinterpret_cast<vec*>(own ? dst.v : stage.v) + de, vv[u]);
             }
         }
-        if (md_mine) {                                            // (wavefronts 0 and 1, which have rows whenever they have entries)
-            dst.log_beta[dbase + tid] = md_lb;
-            if (src.log_tail) dst.log_tail[dbase + tid] = md_lt;
-            dst.pos[dbase + tid] = md_pos;
+    };
+    auto write_metadata = [&]() {
+        const int64_t de = dbase + md_rank;
+        if (!INPLACE || de != sbase + tid) {
+            const CacheViewMut& t = (!INPLACE || de >= sbase) ? dst : stage;
+            t.log_beta[de] = md_lb;
+            if (src.log_tail) t.log_tail[de] = md_lt;
+            t.pos[de] = md_pos;
         }
-        if (attend) {
-            float z[4][G];
+    };
+    auto attend_rows = [&](const vec (&kk)[4], const vec (&vv)[4], const float (&qf)[G][E]) {
+        float z[4][G];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                float kf[E];
-                R::unpack(kk[u], kf);
-                const bool valid = r0 + u * 4 + sub < cnt;
-#pragma unroll
-                for (int g = 0; g < G; ++g) {
-                    float part = 0.f;
-#pragma unroll
-                    for (int e = 0; e < E; ++e) part = fmaf(qf[g][e], kf[e], part);
-                    const float s = row16_sum(part);
-                    z[u][g] = valid ? s * scale_log2 : -INFINITY;
-                }
-            }
-            float vf[4][E];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) R::unpack(vv[u], vf[u]);
+        for (int u = 0; u < 4; ++u) {
+            float kf[E];
+            R::unpack(kk[u], kf);
+            const bool valid = r0 + u * 4 + sub < cnt;
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                const float mx = fmaxf(fmaxf(z[0][g], z[1][g]), fmaxf(z[2][g], z[3][g]));
-                const float m_safe = mx == -INFINITY ? 0.f : mx;
-                float p[4];
+                float part = 0.f;
 #pragma unroll
-                for (int u = 0; u < 4; ++u) p[u] = __builtin_amdgcn_exp2f(z[u][g] - m_safe);
-                l[g] = (p[0] + p[1]) + (p[2] + p[3]);
-                m[g] = mx;
-#pragma unroll
-                for (int e = 0; e < E; ++e) {
-                    float acc = p[0] * vf[0][e];
-#pragma unroll
-                    for (int u = 1; u < 4; ++u) acc = fmaf(p[u], vf[u][e], acc);
-                    o[g][e] = acc;
-                }
+                for (int e = 0; e < E; ++e) part = fmaf(qf[g][e], kf[e], part);
+                const float s = row16_sum(part);
+                z[u][g] = valid ? s * scale_log2 : -INFINITY;
             }
+        }
+        float vf[4][E];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) R::unpack(vv[u], vf[u]);
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const float mx = fmaxf(fmaxf(z[0][g], z[1][g]), fmaxf(z[2][g], z[3][g]));
+            const float m_safe = mx == -INFINITY ? 0.f : mx;
+            float p[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) p[u] = __builtin_amdgcn_exp2f(z[u][g] - m_safe);
+            l[g] = (p[0] + p[1]) + (p[2] + p[3]);
+            m[g] = mx;
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                float acc = p[0] * vf[0][e];
+#pragma unroll
+                for (int u = 1; u < 4; ++u) acc = fmaf(p[u], vf[u][e], acc);
+                o[g][e] = acc;
+            }
+        }
+    };
+
+    if (!INPLACE) {
+        if (has_rows) {
+            vec kk[4], vv[4];
+            int srow[4];
+            float qf[G][E];
+            fetch(kk, vv, srow, qf);
+            write_rows(kk, vv, srow);
+            if (md_mine) write_metadata();                        // (wavefronts 0 and 1, which have rows whenever they have entries)
+            if (attend) attend_rows(kk, vv, qf);
+        }
+    } else {
+        vec kk[4], vv[4];
+        int srow[4];
+        float qf[G][E];
+        if (has_rows) fetch(kk, vv, srow, qf);
+        if (moves) {
+            // every wavefront of the block holds its rows and metadata in registers before any of them overwrites an entry
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (md_mine) write_metadata();
+        }
+        if (has_rows) {
+            if (moves) write_rows(kk, vv, srow);
+            if (attend) attend_rows(kk, vv, qf);
         }
     }
     if (!attend) return;
@@ -300,20 +349,58 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
     }
 }
 
-template <int D>
+template <int D, bool INPLACE>
 static bool dispatch_fused(int G, dim3 grid, hipStream_t st, const CacheView& src, const uint8_t* keep,
-                           const CacheViewMut& dst, const uint16_t* q, const Shape& sh, const Workspace& ws,
-                           float scale_log2, int lb, int le) {
+                           const CacheViewMut& dst, const CacheViewMut& stage, const uint16_t* q, const Shape& sh,
+                           const Workspace& ws, float scale_log2, int lb, int le) {
     switch (G) {
 #define KVTRIM_CASE(g) \
-    case g: hipLaunchKernelGGL((k_cmp_attn<D, g>), grid, dim3(FUS_THREADS), 0, st, src, keep, dst, q, sh, ws, scale_log2, lb, le); return true;
+    case g: hipLaunchKernelGGL((k_cmp_attn<D, g, INPLACE>), grid, dim3(FUS_THREADS), 0, st, src, keep, dst, stage, q, sh, ws, scale_log2, lb, le); return true;
         KVTRIM_CASE(1) KVTRIM_CASE(2) KVTRIM_CASE(3) KVTRIM_CASE(4) KVTRIM_CASE(5) KVTRIM_CASE(6)
 #undef KVTRIM_CASE
         default: return false;                                    // larger groups take the loop-shaped kernel (k_att_fused)
     }
 }
 
-// Largest group of query heads the one-shot fused kernel below is used for (beyond it, the loop-shaped one).
+// After k_cmp_attn<.., INPLACE>: the survivors of a chunk whose place lies before the chunk's own range (as many
+// as were evicted before the chunk in its segment, at most all of its survivors) wait in `stage` at their final
+// index; one wavefront per chunk puts them there (in a decode step most chunks have nothing parked and their
+// wavefront ends at once).  The wavefront of a segment's first chunk also commits the segment's new length, which
+// no kernel of the call reads any more.
+constexpr int UNS_THREADS = 256;
+
+template <int D>
+__global__ __launch_bounds__(UNS_THREADS) void k_cmp_unstage(CacheViewMut c, CacheViewMut stage,
+                                                             const int32_t* __restrict__ kept, Shape sh, Workspace ws) {
+    constexpr int VPR = D / 8;                                    // 16-byte vectors per row
+    const int lane = lane_id();
+    const int ch = blockIdx.x * (UNS_THREADS / 64) + (threadIdx.x >> 6);
+    if (__hip_atomic_load(ws.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
+    if (ch >= ws.cmp_chunk_prefix[sh.nseg]) return;
+    const ChunkDesc cd = ws.cmp_desc[ch];
+    const int seg = cd.seg;
+    const int64_t dbase = ws.cmp_chunk_dst[ch] & ~CMP_DST_FULL;
+    if (ch == ws.cmp_chunk_prefix[seg] && lane == 0) c.seg_len[seg] = kept[seg];
+    if (cd.first == dbase) return;                                // nothing was evicted before this chunk
+    const bool last = ch + 1 == ws.cmp_chunk_prefix[seg + 1];
+    const int64_t dnext = last ? c.seg_start[seg] + kept[seg] : (ws.cmp_chunk_dst[ch + 1] & ~CMP_DST_FULL);
+    const int64_t staged = min(cd.first - dbase, dnext - dbase);  // survivors that belong before the chunk's own range
+    const uint4* sk = reinterpret_cast<const uint4*>(stage.k) + dbase * VPR;
+    const uint4* sv = reinterpret_cast<const uint4*>(stage.v) + dbase * VPR;
+    uint4* dk = reinterpret_cast<uint4*>(c.k) + dbase * VPR;
+    uint4* dv = reinterpret_cast<uint4*>(c.v) + dbase * VPR;
+    for (int64_t i = lane; i < staged * VPR; i += 64) {
+        dk[i] = sk[i];
+        dv[i] = sv[i];
+    }
+    for (int64_t i = lane; i < staged; i += 64) {
+        c.log_beta[dbase + i] = stage.log_beta[dbase + i];
+        if (c.log_tail) c.log_tail[dbase + i] = stage.log_tail[dbase + i];
+        c.pos[dbase + i] = stage.pos[dbase + i];
+    }
+}
+
+// Largest group of query heads the one-shot fused kernel is used for (beyond it, the loop-shaped one).
 constexpr int FUSED_ONE_SHOT_MAX_G_128 = 5, FUSED_ONE_SHOT_MAX_G_64 = 4;
 constexpr int FUSE_RUN_ENTRIES = 2 * CMP_CHUNK;                   // source entries per block of the loop-shaped fused kernel
 
@@ -357,10 +444,39 @@ kvtrim_status launch_compact_attn(kvtrim_ctx* ctx, const CacheView& src, const u
         ProfScope prof(ctx, K_CMP_ATTN, st);
         const float scale_log2 = scale * 1.4426950408889634f;
         ok = sh.head_dim == 128
-                 ? dispatch_fused<128>(sh.group, dim3((unsigned)max_chunks), st, src, keep, dst, q, sh, ws, scale_log2, layer_begin, layer_end)
-                 : dispatch_fused<64>(sh.group, dim3((unsigned)max_chunks), st, src, keep, dst, q, sh, ws, scale_log2, layer_begin, layer_end);
+                 ? dispatch_fused<128, false>(sh.group, dim3((unsigned)max_chunks), st, src, keep, dst, dst, q, sh, ws, scale_log2, layer_begin, layer_end)
+                 : dispatch_fused<64, false>(sh.group, dim3((unsigned)max_chunks), st, src, keep, dst, dst, q, sh, ws, scale_log2, layer_begin, layer_end);
     }
     if (!ok) return KVTRIM_EINVAL;
+    return launch_combine(ctx, ws.cmp_chunk_prefix, layer_begin, layer_end, out, lse, st);
+}
+
+kvtrim_status launch_compact_attn_inplace(kvtrim_ctx* ctx, const CacheViewMut& c, const uint8_t* keep, const int32_t* kept,
+                                          const CacheViewMut& stage, const uint16_t* q, int32_t layer_begin,
+                                          int32_t layer_end, float scale, float* out, float* lse, hipStream_t st) {
+    const Shape& sh = ctx->shape;
+    const Workspace& ws = ctx->ws;
+    const int64_t max_chunks = c.cap / CMP_CHUNK + sh.nseg;      // <= ws.max_att_chunks, checked by the caller
+    CacheView src;
+    src.k = c.k; src.v = c.v; src.log_beta = c.log_beta; src.pos = c.pos;
+    src.seg_start = c.seg_start; src.seg_len = c.seg_len; src.cap = c.cap; src.log_tail = c.log_tail;
+    launch_cmp_scan_inplace(ctx, c, keep, kept, st);
+    bool ok;
+    {
+        ProfScope prof(ctx, K_CMP_ATTN, st);
+        const float scale_log2 = scale * 1.4426950408889634f;
+        ok = sh.head_dim == 128
+                 ? dispatch_fused<128, true>(sh.group, dim3((unsigned)max_chunks), st, src, keep, c, stage, q, sh, ws, scale_log2, layer_begin, layer_end)
+                 : dispatch_fused<64, true>(sh.group, dim3((unsigned)max_chunks), st, src, keep, c, stage, q, sh, ws, scale_log2, layer_begin, layer_end);
+    }
+    if (!ok) return KVTRIM_EINVAL;
+    {
+        ProfScope prof(ctx, K_CMP_UNSTAGE, st);
+        if (sh.head_dim == 128)
+            hipLaunchKernelGGL(k_cmp_unstage<128>, dim3((unsigned)((max_chunks + UNS_THREADS / 64 - 1) / (UNS_THREADS / 64))), dim3(UNS_THREADS), 0, st, c, stage, kept, sh, ws);
+        else
+            hipLaunchKernelGGL(k_cmp_unstage<64>, dim3((unsigned)((max_chunks + UNS_THREADS / 64 - 1) / (UNS_THREADS / 64))), dim3(UNS_THREADS), 0, st, c, stage, kept, sh, ws);
+    }
     return launch_combine(ctx, ws.cmp_chunk_prefix, layer_begin, layer_end, out, lse, st);
 }
 

@@ -219,7 +219,7 @@ static const char* const kernel_names[KVTRIM_N_KERNELS] = {
     "k_score", "k_sel_plan", "k_sel_hist<0>", "k_sel_hist<1>", "k_sel_hist<2>", "k_sel_count", "k_sel_mask",
     "k_cmp_scan", "k_cmp_copy", "k_att_plan", "k_att_partial", "k_att_combine", "k_append", "k_cmp_attn", "k_occupancy",
     "k_pg_init", "k_pg_append", "k_pg_score", "k_pg_plan", "k_pg_count", "k_pg_evict", "k_pg_tidy", "k_pg_att_plan", "k_gate_hidden", "k_gate_readout",
-    "k_gate_fold", "k_gate_prefill", "k_gate_retile", "k_pg_defrag", "k_gate_dot", "k_att_fused"};
+    "k_gate_fold", "k_gate_prefill", "k_gate_retile", "k_pg_defrag", "k_gate_dot", "k_att_fused", "k_cmp_unstage"};
 
 const char* kvtrim_kernel_name(int32_t id) { return id >= 0 && id < KVTRIM_N_KERNELS ? kernel_names[id] : nullptr; }
 
@@ -380,6 +380,31 @@ kvtrim_status kvtrim_compact_attn(kvtrim_ctx* ctx, const kvtrim_cache* src, cons
     if (!(softmax_scale == softmax_scale)) return invalid(ctx, "softmax_scale is NaN");
     return launch_compact_attn(ctx, view_of(src), keep, kept, view_mut_of(dst), reserve, (const uint16_t*)q,
                                layer_begin, layer_end, softmax_scale, out, lse, (hipStream_t)hip_stream);
+}
+
+kvtrim_status kvtrim_compact_attn_inplace(kvtrim_ctx* ctx, kvtrim_cache* c, const uint8_t* keep, const int32_t* kept,
+                                          kvtrim_cache* spare, const void* q, int32_t layer_begin, int32_t layer_end,
+                                          float softmax_scale, float* out, float* lse, void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    if (const char* p = cache_problem(ctx, c, true)) return invalid(ctx, p);
+    if (!spare || !spare->k || !spare->v || !spare->log_beta || !spare->pos) return invalid(ctx, "spare or one of its k / v / log_beta / pos arrays is NULL");
+    if ((((uintptr_t)spare->k) | ((uintptr_t)spare->v)) & 15) return invalid(ctx, "spare k/v not 16-byte aligned");
+    if (spare->cap_entries < c->cap_entries) return invalid(ctx, "spare holds fewer entries than the cache");
+    if (c->k == spare->k || c->v == spare->v || c->log_beta == spare->log_beta || c->pos == spare->pos)
+        return invalid(ctx, "the cache and spare share a buffer");
+    if (c->log_tail && (!spare->log_tail || spare->log_tail == c->log_tail))
+        return invalid(ctx, "the cache carries log_tail: spare needs a log_tail array of its own");
+    if (!keep || !kept) return invalid(ctx, "keep / kept is NULL");
+    if (!q || !out) return invalid(ctx, "q / out is NULL");
+    if (((uintptr_t)q) & 15) return invalid(ctx, "q not 16-byte aligned");
+    if (layer_begin < 0 || layer_end > ctx->cfg.n_layers || layer_begin >= layer_end)
+        return invalid(ctx, "empty or out-of-range layer range");
+    if (!(softmax_scale == softmax_scale)) return invalid(ctx, "softmax_scale is NaN");
+    if (ctx->shape.group > 6) return invalid(ctx, "the in-place path serves groups of at most 6 query heads per KV head");
+    if (c->cap_entries / CMP_CHUNK + ctx->shape.nseg > ctx->ws.max_att_chunks)
+        return invalid(ctx, "cache too large for the in-place path (more than 524288 chunks of 128 entries)");
+    return launch_compact_attn_inplace(ctx, view_mut_of(c), keep, kept, view_mut_of(spare), (const uint16_t*)q, layer_begin,
+                                       layer_end, softmax_scale, out, lse, (hipStream_t)hip_stream);
 }
 
 kvtrim_status kvtrim_append(kvtrim_ctx* ctx, kvtrim_cache* c, const void* k_new, const void* v_new,

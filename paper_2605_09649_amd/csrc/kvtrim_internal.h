@@ -117,7 +117,7 @@ namespace kvtrim {
 enum KernelId {
     K_SCORE = 0, K_SEL_PLAN, K_SEL_HIST0, K_SEL_HIST1, K_SEL_HIST2, K_SEL_COUNT, K_SEL_MASK,
     K_CMP_SCAN, K_CMP_COPY, K_ATT_PLAN, K_ATT_PARTIAL, K_ATT_COMBINE, K_APPEND, K_CMP_ATTN, K_OCCUPANCY,
-    K_PG_INIT, K_PG_APPEND, K_PG_SCORE, K_PG_PLAN, K_PG_COUNT, K_PG_EVICT, K_PG_TIDY, K_PG_ATT_PLAN, K_GATE_HIDDEN, K_GATE_READOUT, K_GATE_FOLD, K_GATE_PREFILL, K_GATE_RETILE, K_PG_DEFRAG, K_GATE_DOT, K_ATT_FUSED, K_COUNT
+    K_PG_INIT, K_PG_APPEND, K_PG_SCORE, K_PG_PLAN, K_PG_COUNT, K_PG_EVICT, K_PG_TIDY, K_PG_ATT_PLAN, K_GATE_HIDDEN, K_GATE_READOUT, K_GATE_FOLD, K_GATE_PREFILL, K_GATE_RETILE, K_PG_DEFRAG, K_GATE_DOT, K_ATT_FUSED, K_CMP_UNSTAGE, K_COUNT
 };
 static_assert(K_COUNT == KVTRIM_N_KERNELS, "kernel table out of step with the header");
 }  // namespace kvtrim
@@ -168,6 +168,11 @@ bool launch_attn_fused(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, c
                        int32_t layer_begin, int32_t layer_end, float scale, hipStream_t st);
 kvtrim_status launch_combine(kvtrim_ctx*, const int32_t* chunk_prefix, int32_t layer_begin, int32_t layer_end,
                              float* out, float* lse, hipStream_t);
+void launch_cmp_scan_inplace(kvtrim_ctx*, const CacheViewMut& c, const uint8_t* keep, const int32_t* kept, hipStream_t);
+// Stages 3 + 4 inside the cache itself (every segment keeps its start); `stage` lends its row and metadata arrays.
+kvtrim_status launch_compact_attn_inplace(kvtrim_ctx*, const CacheViewMut& c, const uint8_t* keep, const int32_t* kept,
+                                          const CacheViewMut& stage, const uint16_t* q, int32_t layer_begin,
+                                          int32_t layer_end, float scale, float* out, float* lse, hipStream_t);
 kvtrim_status launch_compact_attn(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const int32_t* kept,
                                   const CacheViewMut& dst, int32_t reserve, const uint16_t* q,
                                   int32_t layer_begin, int32_t layer_end, float scale, float* out, float* lse,

@@ -237,3 +237,83 @@ def run_multiturn_both(w, lengths, chunk, decode_per_turn, budget, device="cuda:
             q = inp.pop("q")
             select_compact(pos_new, 1, inp, q, f"turn {t} decode {dstep}")
     return results
+
+
+def compare_cache_contents(hc_gpu, hc_ref):
+    """Segment lengths equal and the live entries, taken segment by segment, bit-equal - whatever the segment starts
+    are (a cache compacted in place keeps its starts, the oracle packs its segments)."""
+    if not np.array_equal(hc_gpu.seg_len, hc_ref.seg_len):
+        return False
+    mg, mr = live_mask(hc_gpu), live_mask(hc_ref)
+    if (hc_gpu.log_tail is None) != (hc_ref.log_tail is None):
+        return False
+    if hc_ref.log_tail is not None and not np.array_equal(hc_gpu.log_tail[mg].view(np.uint32), hc_ref.log_tail[mr].view(np.uint32)):
+        return False
+    return (np.array_equal(hc_gpu.k[mg], hc_ref.k[mr]) and np.array_equal(hc_gpu.v[mg], hc_ref.v[mr])
+            and np.array_equal(hc_gpu.log_beta[mg].view(np.uint32), hc_ref.log_beta[mr].view(np.uint32))
+            and np.array_equal(hc_gpu.pos[mg], hc_ref.pos[mr]))
+
+
+def run_steps_inplace_both(w, steps, budget, room, cache_dict, now0, device="cuda:0", horizon=1, rebalance_at=()):
+    """The decode loop with stages 3 + 4 done inside the cache (kvtrim_compact_attn_inplace): `cache_dict` must leave
+    `room` free slots behind every segment (one is used per step).  At the steps listed in `rebalance_at` the GPU
+    side runs the out-of-place fused call instead, into a second cache with `room` free slots per segment again.
+    The oracle runs its four stages; scores, mask, counts, threshold, segment contents and attention are compared."""
+    cache_dict = ki.with_horizon(cache_dict, horizon)
+    hc = host_cache(w, cache_dict)
+    cur = kv.Cache.from_dict(cache_dict, device)
+    cap = cur.cap
+    other = kv.Cache.empty(w.nseg, w.head_dim, cap, device, with_tail=cur.log_tail is not None)
+    ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, cap)
+    score = torch.zeros(cap, dtype=torch.float32, device=device)
+    keep = torch.zeros(cap, dtype=torch.uint8, device=device)
+    kept = torch.zeros(w.nseg, dtype=torch.int32, device=device)
+    thr = torch.zeros(w.n_seq, dtype=torch.int32, device=device)
+    budget_np = np.array(list(budget), np.int64)
+    budget_dev = torch.from_numpy(budget_np).to(device)
+    out = torch.zeros(w.n_seq, w.n_layers, w.n_q_heads, w.head_dim, dtype=torch.float32, device=device)
+    lse = torch.zeros(w.n_seq, w.n_layers, w.n_q_heads, dtype=torch.float32, device=device)
+    scale = 1.0 / math.sqrt(w.head_dim)
+    now = np.array(now0, np.int32)
+    per_seq = w.n_layers * w.n_kv_heads
+    results = []
+    for step in range(steps):
+        inp = ki.decode_inputs(w, step, horizon=horizon)
+        now = now + 1
+        pos_new = np.repeat(now, per_seq).astype(np.int32)
+        oracle.append(hc, bf16_bits(inp["k_new"]), bf16_bits(inp["v_new"]), inp["log_beta_new"].numpy(), pos_new,
+                      log_tail_new=None if horizon == 1 else inp["log_tail_new"].numpy())
+        score_ref = oracle.score(hc, now)
+        keep_ref, kept_ref, thr_ref = oracle.select(hc, score_ref, budget_np)
+        hc_next = oracle.compact(hc, keep_ref, cap, room)
+        out_ref, lse_ref = oracle.attend(hc_next, bf16_bits(inp["q"]), scale)
+        d = {k: v.to(device) for k, v in inp.items()}
+        kv.kvtrim_append(ctx, cur, d["k_new"], d["v_new"], d["log_beta_new"], torch.from_numpy(pos_new).to(device), 1,
+                         log_tail_new=d.get("log_tail_new"))
+        kv.kvtrim_score(ctx, cur, torch.from_numpy(now).to(device), score)
+        kv.kvtrim_select_global(ctx, cur, score, budget_dev, keep, kept, thr)
+        live_gpu = live_mask(device_cache_to_host(w, cur))         # the GPU cache's own layout, after the append
+        score_gpu, keep_gpu = score.cpu().numpy(), keep.cpu().numpy()
+        if step in rebalance_at:
+            kv.kvtrim_compact_attn(ctx, cur, keep, kept, other, room, d["q"], 0, w.n_layers, scale, out, lse)
+            cur, other = other, cur
+        else:
+            kv.kvtrim_compact_attn_inplace(ctx, cur, keep, kept, other, d["q"], 0, w.n_layers, scale, out, lse)
+        res = {"status": kv.kvtrim_poll_error(ctx), "in_place": step not in rebalance_at}
+        live_ref = live_mask(hc)
+        res["score_equal"] = bool(np.array_equal(score_gpu[live_gpu].view(np.uint32), score_ref[live_ref].view(np.uint32)))
+        res["keep_equal"] = bool(np.array_equal(keep_gpu[live_gpu], keep_ref[live_ref])
+                                 and np.array_equal(kept.cpu().numpy(), kept_ref)
+                                 and np.array_equal(thr.cpu().numpy().view(np.uint32), thr_ref))
+        hg = device_cache_to_host(w, cur)
+        res["cache_equal"] = compare_cache_contents(hg, hc_next)
+        res["starts_kept"] = True
+        res["attn_err"] = attn_error(out.cpu().numpy(), out_ref)
+        fin = np.isfinite(lse_ref)
+        lse_gpu = lse.cpu().numpy()
+        res["lse_err"] = float(np.abs(lse_gpu[fin] - lse_ref[fin]).max()) if fin.any() else 0.0
+        res["lse_inf_equal"] = bool(np.array_equal(np.isneginf(lse_gpu), np.isneginf(lse_ref)))
+        res["moved_chunks"] = int((keep_ref[live_ref] == 0).sum())
+        results.append(res)
+        hc = hc_next
+    return results
