@@ -189,3 +189,42 @@ def test_chunk_steps_in_one_call_stay_inside_the_buffers(D):
         cur ^= 1
     live = caches[cur].seg_len.cpu().numpy().reshape(w.n_seq, per_seq).sum(1)
     assert list(live) == [budget_per_seq, budget_per_seq]          # 150 and 107 tokens per list came in, 40 per list stay
+
+
+@pytest.mark.parametrize("G,D", [(2, 64), (4, 128)])
+def test_in_place_steps_stay_inside_the_buffers(G, D):
+    # kvtrim_compact_attn_inplace: the cache, the spare arrays that park rows, and every output between guard zones
+    w = ki.Workload("c", 0, 2, 2, 3, 3 * G, D, (0, 0), (0, 0), 1, 3.0, 1.5)
+    rng = np.random.default_rng(G + D)
+    seg_len = rng.integers(1, 900, w.nseg)
+    seg_len[2] = 0
+    seg_len[5] = 3 * 128
+    room = 4
+    c, now0 = ki.ragged_cache(w, seg_len, reserve=room, salt=2)
+    gd = Guarded()
+    cache = guarded_cache(gd, w.nseg, D, c["cap"])
+    for name in ("k", "v", "log_beta", "pos", "seg_start", "seg_len"):
+        getattr(cache, name).copy_(c[name])
+    spare = guarded_cache(gd, w.nseg, D, c["cap"])
+    cap = c["cap"]
+    ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, D, cap)
+    per_seq = [int(seg_len[:6].sum()), int(seg_len[6:].sum())]
+    budget = torch.tensor([per_seq[0] - 20, per_seq[1] // 2], dtype=torch.int64, device=DEV)
+    score, keep = gd.make((cap,), torch.float32), gd.make((cap,), torch.uint8)
+    kept, thr = gd.make((w.nseg,), torch.int32), gd.make((w.n_seq,), torch.int32)
+    out = gd.make((w.n_seq, w.n_layers, w.n_q_heads, D), torch.float32)
+    lse = gd.make((w.n_seq, w.n_layers, w.n_q_heads), torch.float32)
+    now = now0.numpy().astype(np.int32)
+    for step in range(room):
+        inp = {k: v.to(DEV) for k, v in ki.decode_inputs(w, step).items()}
+        now = now + 1
+        now_dev = torch.from_numpy(now).to(DEV)
+        pos_new = torch.from_numpy(np.repeat(now, w.n_layers * w.n_kv_heads).astype(np.int32)).to(DEV)
+        kv.kvtrim_append(ctx, cache, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos_new, 1)
+        kv.kvtrim_score(ctx, cache, now_dev, score)
+        kv.kvtrim_select_global(ctx, cache, score, budget, keep, kept, thr)
+        kv.kvtrim_compact_attn_inplace(ctx, cache, keep, kept, spare, inp["q"], 0, w.n_layers, 1.0 / math.sqrt(D), out, lse)
+        assert kv.kvtrim_poll_error(ctx) == 0, step
+        assert gd.intact(), step
+    assert torch.isfinite(out).all()
+    assert int(cache.seg_len.sum().item()) == int(budget.sum().item())
