@@ -665,6 +665,49 @@ def main():
                                             "(OpenMP over segments), the other stages run on one"}
         result["parity_on_sampled_step"] = {"steps": CPU_STEPS, "select_compact_bit_exact": ok_sel and ok_cache,
                                             "attn_max_norm_rel_err": err}
+    # ---- the same steps with stages 3+4 done inside the cache (kvtrim_compact_attn_inplace), timed beside the metric's
+    # out-of-place step: ROOM free slots behind every segment, every ROOM-th step out of place to even them out
+    ROOM, K2 = 64, min(K, 128)
+    cap_room = n_ret + w.nseg * ROOM + 8
+    plain = not (args.paged or args.unfused or args.inplace or args.graph or args.kernel_times or args.pmc_calibration)
+    if plain and w.group <= 6 and cap_room <= cap:
+        s0 = n_steps
+        extra, extra_now, extra_pos = [], [], []
+        for s in range(s0, s0 + K2 + 1):
+            extra.append(ki.decode_inputs(w, s, device=dev, horizon=args.horizon))
+            now = now0 + s + 1
+            extra_now.append(torch.from_numpy(now).to(dev))
+            extra_pos.append(torch.from_numpy(np.repeat(now, per_seq).astype(np.int32)).to(dev))
+        big = [kv.Cache.empty(w.nseg, w.head_dim, cap_room, dev, with_tail=args.horizon != 1) for _ in range(2)]
+        cur, other = state["src"], big[0]
+
+        def step_room(i, in_place):
+            nonlocal cur, other
+            inp = extra[i]
+            kv.kvtrim_append(ctx, cur, inp["k_new"], inp["v_new"], inp["log_beta_new"], extra_pos[i], 1,
+                             log_tail_new=inp.get("log_tail_new"))
+            kv.kvtrim_score(ctx, cur, extra_now[i], score)
+            kv.kvtrim_select_global(ctx, cur, score, budget, keep, kept, thr)
+            if in_place:
+                kv.kvtrim_compact_attn_inplace(ctx, cur, keep, kept, other, inp["q"], 0, w.n_layers, scale, out, lse)
+            else:
+                kv.kvtrim_compact_attn(ctx, cur, keep, kept, other, ROOM, inp["q"], 0, w.n_layers, scale, out, lse)
+                cur, other = other, (big[1] if other is big[0] else big[0])
+
+        step_room(0, False)                                        # into a cache with room behind every segment
+        torch.cuda.synchronize()
+        t_begin = time.perf_counter()
+        for i in range(1, K2 + 1):
+            step_room(i, i % ROOM != 0)
+        torch.cuda.synchronize()
+        ms_room = (time.perf_counter() - t_begin) * 1e3 / K2
+        assert kv.kvtrim_poll_error(ctx) == 0 and int(kept.sum().item()) == n_ret and bool(torch.isfinite(out).all())
+        log(f"[bench] the same steps compacting in place: {ms_room:.4f} ms/step ({1e3 / ms_room:.0f} steps/s)")
+        result["in_place_variant"] = {
+            "ms_per_step": ms_room, "value": 1e3 / ms_room, "unit": "steps/s", "steps": K2, "room": ROOM,
+            "what": "append, score, select_global, compact_attn_inplace: a row moves only if an entry before it in its segment "
+                    "was evicted; every 64th step is out of place (inside the timed steps); checked against the oracle by "
+                    "bench.py --inplace 64 and tests/test_gpu_inplace.py"}
     print(json.dumps(result), flush=True)
 
 
