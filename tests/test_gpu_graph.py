@@ -20,15 +20,16 @@ class Loop:
     """Device state of one decode loop with static input buffers (so that a captured step finds its inputs at
     fixed addresses)."""
 
-    def __init__(self, w, paged):
-        self.w, self.paged = w, paged
+    def __init__(self, w, paged, inplace=False):
+        self.w, self.paged, self.inplace = w, paged, inplace
+        self.room = 8 if inplace else 1                           # free slots behind every segment after the first step
         pre = ki.prefill_cache(w, reserve=1)
         self.src = kv.Cache.from_dict(pre, DEV)
         total = int(pre["seg_len"].sum())
         B = sum(w.budget)
         cap = max(self.src.cap, B + 64 * w.nseg)
         self.ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, cap)
-        self.spare = [kv.Cache.empty(w.nseg, w.head_dim, B + 2 * w.nseg + 8, DEV) for _ in range(2)]
+        self.spare = [kv.Cache.empty(w.nseg, w.head_dim, B + (self.room + 1) * w.nseg + 8, DEV) for _ in range(2)]
         n_pages = (B + kv.PAGE_SIZE - 1) // kv.PAGE_SIZE + 3 * w.nseg + 8
         self.pc = kv.PagedCache(w.nseg, w.head_dim, n_pages, n_pages, DEV) if paged else None
         cap = max(cap, n_pages * kv.PAGE_SIZE)
@@ -65,7 +66,7 @@ class Loop:
             kv.kvtrim_paged_build(ctx, self.src, self.keep, self.kept, self.pc)
             kv.kvtrim_paged_attn(ctx, self.pc, i["q"], 0, w.n_layers, self.scale, self.out[0])
         else:
-            kv.kvtrim_compact_attn(ctx, self.src, self.keep, self.kept, self.spare[0], 1, i["q"], 0, w.n_layers,
+            kv.kvtrim_compact_attn(ctx, self.src, self.keep, self.kept, self.spare[0], self.room, i["q"], 0, w.n_layers,
                                    self.scale, self.out[0])
             self.cur, self.flip = self.spare[0], 1
 
@@ -82,6 +83,10 @@ class Loop:
             kv.kvtrim_append(ctx, self.cur, i["k_new"], i["v_new"], i["log_beta_new"], self.pos[slot], 1)
             kv.kvtrim_score(ctx, self.cur, self.now[slot], self.score)
             kv.kvtrim_select_global(ctx, self.cur, self.score, self.budget, self.keep, self.kept, self.thr)
+            if self.inplace:                                      # the other cache only lends its arrays
+                kv.kvtrim_compact_attn_inplace(ctx, self.cur, self.keep, self.kept, dst, i["q"], 0, w.n_layers, self.scale,
+                                               self.out[slot])
+                return
             kv.kvtrim_compact_attn(ctx, self.cur, self.keep, self.kept, dst, 1, i["q"], 0, w.n_layers, self.scale,
                                    self.out[slot])
             self.cur, self.flip = dst, self.flip ^ 1
@@ -113,10 +118,11 @@ def same(a, b):
                               b[k].view(np.uint8) if b[k].dtype.kind == "f" else b[k]) for k in a) and a.keys() == b.keys()
 
 
-@pytest.mark.parametrize("paged", [False, True])
+@pytest.mark.parametrize("paged", [False, True, "inplace"])
 def test_two_captured_steps_replayed_three_times_match_the_eager_loop(paged):
     w = ki.workload("tiny", prefill=900)
-    eager, graphed = Loop(w, paged), Loop(w, paged)
+    inplace, paged = paged == "inplace", paged is True
+    eager, graphed = Loop(w, paged, inplace), Loop(w, paged, inplace)
     for loop in (eager, graphed):
         loop.first_step()
         assert kv.kvtrim_poll_error(loop.ctx) == 0
