@@ -670,7 +670,7 @@ def main():
     ROOM, K2 = 64, min(K, 128)
     cap_room = n_ret + w.nseg * ROOM + 8
     plain = not (args.paged or args.unfused or args.inplace or args.graph or args.kernel_times or args.pmc_calibration)
-    if plain and w.group <= 6 and cap_room <= cap:
+    if plain and cap_room <= cap:
         s0 = n_steps
         extra, extra_now, extra_pos = [], [], []
         for s in range(s0, s0 + K2 + 1):

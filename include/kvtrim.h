@@ -199,8 +199,8 @@ kvtrim_status kvtrim_compact_attn(kvtrim_ctx *ctx, const kvtrim_cache *src, cons
  * arrays hold at least c->cap_entries entries and are distinct from c's; the call parks a few
  * rows there while it runs (those that move into a region another thread block may still be
  * reading); its contents afterwards are unspecified, its segment tables are not touched.
- * Served for up to 6 query heads per KV head and caches of at most 67 M entries
- * (KVTRIM_EINVAL otherwise).  Device-side errors: KVTRIM_EMISMATCH, KVTRIM_ELAYOUT. */
+ * Served for caches of at most 67 M entries (KVTRIM_EINVAL otherwise).  Device-side errors:
+ * KVTRIM_EMISMATCH, KVTRIM_ELAYOUT. */
 kvtrim_status kvtrim_compact_attn_inplace(kvtrim_ctx *ctx, kvtrim_cache *c, const uint8_t *keep,
                                           const int32_t *kept, kvtrim_cache *spare, const void *q,
                                           int32_t layer_begin, int32_t layer_end, float softmax_scale,

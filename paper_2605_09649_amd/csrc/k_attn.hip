@@ -272,9 +272,18 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
 constexpr int FUSE_RUN = 2 * CMP_CHUNK;      // source entries per block (a multiple of 256; 256 measured best: 426 us
                                              // against 442 / 461 us for 512 / 1024 at 2.1 M entries and G = 8)
 
-template <int D, int G>
+// INPLACE: source and destination are the same cache and every segment keeps its start (tables from
+// launch_cmp_scan_inplace).  A survivor moves left by the number of entries evicted before it, or not at all; the
+// block takes its tiles of 64 survivors in order and, where something moves, lets all four wavefronts finish
+// loading a tile before any of them writes it: a tile's destinations lie at or before its own rows and behind every
+// earlier tile's, never on a later tile's rows.  Survivors whose place lies before the run's own range - where
+// another block may still be reading - go to the same index of `stage`; k_cmp_unstage puts them in place after
+// this kernel has ended.  Rows that stay are not written, and a run that loses nothing and does not move skips
+// the mask and the survivor list altogether.
+template <int D, int G, bool INPLACE>
 __global__ __launch_bounds__(ATT_THREADS) void k_att_fused(CacheView src, const uint8_t* __restrict__ keep,
-                                                           CacheViewMut dst, const uint16_t* __restrict__ q, Shape sh,
+                                                           CacheViewMut dst, CacheViewMut stage,
+                                                           const uint16_t* __restrict__ q, Shape sh,
                                                            Workspace ws, float scale_log2, int layer_begin,
                                                            int layer_end) {
     typedef Frag<D> F;
@@ -296,41 +305,80 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_fused(CacheView src, const 
     const int seg = cd.seg;
     const int64_t sbase = cd.first;                               // first source entry of the run
     const int cmp_ch = ws.cmp_chunk_prefix[seg] + (int)((sbase - src.seg_start[seg]) / CMP_CHUNK);
-    const int64_t dbase = ws.cmp_chunk_dst[cmp_ch] & ~CMP_DST_FULL;   // first destination entry of its survivors
+    const int64_t dflag = ws.cmp_chunk_dst[cmp_ch];
+    const int64_t dbase = dflag & ~CMP_DST_FULL;                  // first destination entry of its survivors
+    // INPLACE: the run loses nothing (both of its chunks are marked) ...
+    const bool ident = INPLACE && (dflag & CMP_DST_FULL) != 0 &&
+                       (cd.n <= CMP_CHUNK || (ws.cmp_chunk_dst[cmp_ch + 1] & CMP_DST_FULL) != 0);
+    const bool moves = !INPLACE || !(ident && dbase == sbase);    // ... and stays where it is; uniform over the block
 
     // survivors of the run, in order: passes of 256 entries, ranks from ballots and wavefront counts
     constexpr int NPASS = FUSE_RUN / ATT_THREADS;
-    bool flag[NPASS];
-    int rank[NPASS];
-#pragma unroll
-    for (int h = 0; h < NPASS; ++h) {
-        const int i = h * ATT_THREADS + tid;
-        flag[h] = i < cd.n && keep[sbase + i] != 0;
-        const uint64_t mask = __ballot(flag[h]);
-        rank[h] = mbcnt(mask);
-        if (lane == 0) s_wcnt[h * NSTREAM + wave] = __popcll(mask);
-    }
-    __syncthreads();
+    static_assert(!INPLACE || NPASS == 1, "the in-place instance keeps one entry's metadata per thread");
     int cnt = 0;
+    float md_lb = 0.f, md_lt = 0.f;
+    int md_pos = 0, md_rank = tid;
+    bool md_mine = false;
+    if (ident) {
+        cnt = cd.n;
+        md_mine = moves && tid < cd.n;
+    } else {
+        bool flag[NPASS];
+        int rank[NPASS];
 #pragma unroll
-    for (int w = 0; w < FUSE_RUN / 64; ++w) {
-        const int c = s_wcnt[w];
-#pragma unroll
-        for (int h = 0; h < NPASS; ++h)
-            if (w < h * NSTREAM + wave) rank[h] += c;
-        cnt += c;
-    }
-#pragma unroll
-    for (int h = 0; h < NPASS; ++h) {
-        if (flag[h]) {
+        for (int h = 0; h < NPASS; ++h) {
             const int i = h * ATT_THREADS + tid;
-            s_list[rank[h]] = i;
-            dst.log_beta[dbase + rank[h]] = src.log_beta[sbase + i];
-            if (src.log_tail) dst.log_tail[dbase + rank[h]] = src.log_tail[sbase + i];
-            dst.pos[dbase + rank[h]] = src.pos[sbase + i];
+            flag[h] = i < cd.n && keep[sbase + i] != 0;
+            const uint64_t mask = __ballot(flag[h]);
+            rank[h] = mbcnt(mask);
+            if (lane == 0) s_wcnt[h * NSTREAM + wave] = __popcll(mask);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < FUSE_RUN / 64; ++w) {
+            const int c = s_wcnt[w];
+#pragma unroll
+            for (int h = 0; h < NPASS; ++h)
+                if (w < h * NSTREAM + wave) rank[h] += c;
+            cnt += c;
+        }
+#pragma unroll
+        for (int h = 0; h < NPASS; ++h) {
+            if (flag[h]) {
+                const int i = h * ATT_THREADS + tid;
+                s_list[rank[h]] = i;
+                if (INPLACE) {
+                    md_mine = true;
+                    md_rank = rank[h];
+                } else {
+                    dst.log_beta[dbase + rank[h]] = src.log_beta[sbase + i];
+                    if (src.log_tail) dst.log_tail[dbase + rank[h]] = src.log_tail[sbase + i];
+                    dst.pos[dbase + rank[h]] = src.pos[sbase + i];
+                }
+            }
         }
     }
-    __syncthreads();
+    if (INPLACE) {
+        // the metadata of every entry of the run is in registers before any of it is overwritten
+        if (md_mine) {
+            md_lb = src.log_beta[sbase + tid];
+            if (src.log_tail) md_lt = src.log_tail[sbase + tid];
+            md_pos = src.pos[sbase + tid];
+        }
+        if (moves) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            const int64_t de = dbase + md_rank;
+            if (md_mine && de != sbase + tid) {
+                const CacheViewMut& t = de >= sbase ? dst : stage;
+                t.log_beta[de] = md_lb;
+                if (src.log_tail) t.log_tail[de] = md_lt;
+                t.pos[de] = md_pos;
+            }
+        }
+    } else {
+        __syncthreads();
+    }
 
     const int c16 = lane & 15, b4 = lane >> 4;
     const int seq = seg / sh.segs_per_seq, lh = seg % sh.segs_per_seq;
@@ -351,31 +399,39 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_fused(CacheView src, const 
 
     const vec* kp = reinterpret_cast<const vec*>(src.k);
     const vec* vp = reinterpret_cast<const vec*>(src.v);
-    vec* kd = reinterpret_cast<vec*>(dst.k);
-    vec* vd = reinterpret_cast<vec*>(dst.v);
+    const int last = cnt - 1;
+    auto entry_of = [&](int r) { return ident ? r : s_list[r]; };  // entry of the run that survivor r is
 
-    for (int r0 = wave * 16; r0 < cnt; r0 += 64) {
-        const int last = cnt - 1;
+    // the three steps of a wavefront's tile of 16 survivors [r0, r0 + 16)
+    auto load_tile = [&](int r0, vec (&kf)[4], vec (&vf)[4], int& ksrc_e, int (&vsrc_e)[4]) {
         // K in MFMA operand layout: lane -> survivor r0 + c16, vectors 4j + b4
-        const int kr = r0 + c16;
-        const int64_t ksrc = sbase + s_list[min(kr, last)];
-        vec kf[4], vf[4];
+        ksrc_e = entry_of(min(r0 + c16, last));
 #pragma unroll
-        for (int j = 0; j < 4; ++j) kf[j] = kp[ksrc * VPR + 4 * j + b4];
+        for (int j = 0; j < 4; ++j) kf[j] = kp[(sbase + ksrc_e) * VPR + 4 * j + b4];
         // V row by row: lane -> survivor r0 + 4*b4 + i, vector c16
 #pragma unroll
-        for (int i = 0; i < 4; ++i) vf[i] = vp[(sbase + s_list[min(r0 + 4 * b4 + i, last)]) * VPR + c16];
-        if (kr < cnt) {
+        for (int i = 0; i < 4; ++i) {
+            vsrc_e[i] = entry_of(min(r0 + 4 * b4 + i, last));
+            vf[i] = vp[(sbase + vsrc_e[i]) * VPR + c16];
+        }
+    };
+    auto store_tile = [&](int r0, const vec (&kf)[4], const vec (&vf)[4], int ksrc_e, const int (&vsrc_e)[4]) {
+        const int kr = r0 + c16;
+        if (kr < cnt && (!INPLACE || dbase + kr != sbase + ksrc_e)) {   // INPLACE: a row that stays is not written
+            vec* kd = reinterpret_cast<vec*>((!INPLACE || dbase + kr >= sbase) ? dst.k : stage.k);
 #pragma unroll
             for (int j = 0; j < 4; ++j) kd[(dbase + kr) * VPR + 4 * j + b4] = kf[j];
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int row = r0 + 4 * b4 + i;
-            if (row < cnt) vd[(dbase + row) * VPR + c16] = vf[i];
+            if (row < cnt && (!INPLACE || dbase + row != sbase + vsrc_e[i])) {
+                vec* vd = reinterpret_cast<vec*>((!INPLACE || dbase + row >= sbase) ? dst.v : stage.v);
+                vd[(dbase + row) * VPR + c16] = vf[i];
+            }
         }
-        if (!attend) continue;
-
+    };
+    auto attend_tile = [&](int r0, const vec (&kf)[4], const vec (&vf)[4]) {
         float4v acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc = F::mma(kf[j], qf[j], acc);
@@ -405,6 +461,30 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_fused(CacheView src, const 
             float vfl[E];
             F::unpack(vf[i], vfl);
             PV<G, E, 0>::run(o, p[i], vfl);
+        }
+    };
+
+    if (!INPLACE) {
+        for (int r0 = wave * 16; r0 < cnt; r0 += 64) {
+            vec kf[4], vf[4];
+            int ke, ve[4];
+            load_tile(r0, kf, vf, ke, ve);
+            store_tile(r0, kf, vf, ke, ve);
+            if (attend) attend_tile(r0, kf, vf);
+        }
+    } else {
+        for (int t0 = 0; t0 < cnt; t0 += 64) {                    // the same trip count in every wavefront
+            const int r0 = t0 + wave * 16;
+            const bool active = r0 < cnt;
+            vec kf[4], vf[4];
+            int ke = 0, ve[4] = {0, 0, 0, 0};
+            if (active) load_tile(r0, kf, vf, ke, ve);
+            if (moves) {
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __syncthreads();
+                if (active) store_tile(r0, kf, vf, ke, ve);
+            }
+            if (active && attend) attend_tile(r0, kf, vf);
         }
     }
     if (!attend) return;
@@ -616,7 +696,7 @@ bool launch_attn_fused(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* kee
     ProfScope prof(ctx, K_ATT_FUSED, st);
     const dim3 grid((unsigned)max_chunks), block(ATT_THREADS);
 #define KVTRIM_CASE(d, g) \
-    hipLaunchKernelGGL((k_att_fused<d, g>), grid, block, 0, st, src, keep, dst, q, sh, ws, scale_log2, layer_begin, layer_end); return true
+    hipLaunchKernelGGL((k_att_fused<d, g, false>), grid, block, 0, st, src, keep, dst, dst, q, sh, ws, scale_log2, layer_begin, layer_end); return true
     if (sh.head_dim == 128) {
         switch (sh.group) {
             case 5: KVTRIM_CASE(128, 5);
@@ -631,6 +711,36 @@ bool launch_attn_fused(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* kee
         case 6: KVTRIM_CASE(64, 6);
         case 7: KVTRIM_CASE(64, 7);
         case 8: KVTRIM_CASE(64, 8);
+        default: return false;
+    }
+#undef KVTRIM_CASE
+}
+
+// The loop-shaped pass inside the cache (k_att_fused<.., INPLACE>): the in-place compaction tables must be in the
+// workspace (launch_cmp_scan_inplace).  Returns false when the group size has no instance.
+bool launch_attn_fused_inplace(kvtrim_ctx* ctx, const CacheViewMut& c, const uint8_t* keep, const CacheViewMut& stage,
+                               const uint16_t* q, int32_t layer_begin, int32_t layer_end, float scale, hipStream_t st) {
+    const Shape& sh = ctx->shape;
+    const Workspace& ws = ctx->ws;
+    const int64_t max_chunks = c.cap / FUSE_RUN + sh.nseg;
+    const float scale_log2 = scale * 1.4426950408889634f;
+    CacheView src;
+    src.k = c.k; src.v = c.v; src.log_beta = c.log_beta; src.pos = c.pos;
+    src.seg_start = c.seg_start; src.seg_len = c.seg_len; src.cap = c.cap; src.log_tail = c.log_tail;
+    { ProfScope prof(ctx, K_ATT_PLAN, st);
+      hipLaunchKernelGGL(k_att_plan, dim3(1), dim3(1024), 0, st, src, sh, ws, FUSE_RUN, 0, sh.n_layers, max_chunks); }
+    ProfScope prof(ctx, K_ATT_FUSED, st);
+    const dim3 grid((unsigned)max_chunks), block(ATT_THREADS);
+#define KVTRIM_CASE(d, g) \
+    case g: hipLaunchKernelGGL((k_att_fused<d, g, true>), grid, block, 0, st, src, keep, c, stage, q, sh, ws, scale_log2, layer_begin, layer_end); return true;
+    if (sh.head_dim == 128) {
+        switch (sh.group) {                                       // (smaller groups: the one-shot kernel's in-place instance)
+            KVTRIM_CASE(128, 7) KVTRIM_CASE(128, 8)
+            default: return false;
+        }
+    }
+    switch (sh.group) {
+        KVTRIM_CASE(64, 7) KVTRIM_CASE(64, 8)
         default: return false;
     }
 #undef KVTRIM_CASE

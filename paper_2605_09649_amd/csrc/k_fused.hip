@@ -369,9 +369,12 @@ static bool dispatch_fused(int G, dim3 grid, hipStream_t st, const CacheView& sr
 // no kernel of the call reads any more.
 constexpr int UNS_THREADS = 256;
 
+// run_chunks: chunks per block of the kernel that parked the rows (1: k_cmp_attn, 2: k_att_fused); a block parks
+// only what belongs before its whole run, so the later chunks of a run have nothing parked.
 template <int D>
 __global__ __launch_bounds__(UNS_THREADS) void k_cmp_unstage(CacheViewMut c, CacheViewMut stage,
-                                                             const int32_t* __restrict__ kept, Shape sh, Workspace ws) {
+                                                             const int32_t* __restrict__ kept, Shape sh, Workspace ws,
+                                                             int run_chunks) {
     constexpr int VPR = D / 8;                                    // 16-byte vectors per row
     const int lane = lane_id();
     const int ch = blockIdx.x * (UNS_THREADS / 64) + (threadIdx.x >> 6);
@@ -380,11 +383,13 @@ __global__ __launch_bounds__(UNS_THREADS) void k_cmp_unstage(CacheViewMut c, Cac
     const ChunkDesc cd = ws.cmp_desc[ch];
     const int seg = cd.seg;
     const int64_t dbase = ws.cmp_chunk_dst[ch] & ~CMP_DST_FULL;
-    if (ch == ws.cmp_chunk_prefix[seg] && lane == 0) c.seg_len[seg] = kept[seg];
+    const int first_ch = ws.cmp_chunk_prefix[seg];
+    if (ch == first_ch && lane == 0) c.seg_len[seg] = kept[seg];
     if (cd.first == dbase) return;                                // nothing was evicted before this chunk
-    const bool last = ch + 1 == ws.cmp_chunk_prefix[seg + 1];
-    const int64_t dnext = last ? c.seg_start[seg] + kept[seg] : (ws.cmp_chunk_dst[ch + 1] & ~CMP_DST_FULL);
-    const int64_t staged = min(cd.first - dbase, dnext - dbase);  // survivors that belong before the chunk's own range
+    if ((ch - first_ch) % run_chunks) return;                     // not the first chunk of its run
+    const bool last = ch + run_chunks >= ws.cmp_chunk_prefix[seg + 1];
+    const int64_t dnext = last ? c.seg_start[seg] + kept[seg] : (ws.cmp_chunk_dst[ch + run_chunks] & ~CMP_DST_FULL);
+    const int64_t staged = min(cd.first - dbase, dnext - dbase);  // survivors that belong before the run's own range
     const uint4* sk = reinterpret_cast<const uint4*>(stage.k) + dbase * VPR;
     const uint4* sv = reinterpret_cast<const uint4*>(stage.v) + dbase * VPR;
     uint4* dk = reinterpret_cast<uint4*>(c.k) + dbase * VPR;
@@ -461,8 +466,13 @@ kvtrim_status launch_compact_attn_inplace(kvtrim_ctx* ctx, const CacheViewMut& c
     src.k = c.k; src.v = c.v; src.log_beta = c.log_beta; src.pos = c.pos;
     src.seg_start = c.seg_start; src.seg_len = c.seg_len; src.cap = c.cap; src.log_tail = c.log_tail;
     launch_cmp_scan_inplace(ctx, c, keep, kept, st);
+    // up to six query heads per KV head: the one-shot kernel (long-context workload, G = 4: 0.368 ms per step against
+    // 0.382 with the loop-shaped one); seven and eight: the loop-shaped kernel, as out of place
+    const bool loop_shaped = sh.group > 6;
     bool ok;
-    {
+    if (loop_shaped) {
+        ok = launch_attn_fused_inplace(ctx, c, keep, stage, q, layer_begin, layer_end, scale, st);
+    } else {
         ProfScope prof(ctx, K_CMP_ATTN, st);
         const float scale_log2 = scale * 1.4426950408889634f;
         ok = sh.head_dim == 128
@@ -472,12 +482,14 @@ kvtrim_status launch_compact_attn_inplace(kvtrim_ctx* ctx, const CacheViewMut& c
     if (!ok) return KVTRIM_EINVAL;
     {
         ProfScope prof(ctx, K_CMP_UNSTAGE, st);
+        const dim3 grid((unsigned)((max_chunks + UNS_THREADS / 64 - 1) / (UNS_THREADS / 64)));
+        const int run_chunks = loop_shaped ? 2 : 1;
         if (sh.head_dim == 128)
-            hipLaunchKernelGGL(k_cmp_unstage<128>, dim3((unsigned)((max_chunks + UNS_THREADS / 64 - 1) / (UNS_THREADS / 64))), dim3(UNS_THREADS), 0, st, c, stage, kept, sh, ws);
+            hipLaunchKernelGGL(k_cmp_unstage<128>, grid, dim3(UNS_THREADS), 0, st, c, stage, kept, sh, ws, run_chunks);
         else
-            hipLaunchKernelGGL(k_cmp_unstage<64>, dim3((unsigned)((max_chunks + UNS_THREADS / 64 - 1) / (UNS_THREADS / 64))), dim3(UNS_THREADS), 0, st, c, stage, kept, sh, ws);
+            hipLaunchKernelGGL(k_cmp_unstage<64>, grid, dim3(UNS_THREADS), 0, st, c, stage, kept, sh, ws, run_chunks);
     }
-    return launch_combine(ctx, ws.cmp_chunk_prefix, layer_begin, layer_end, out, lse, st);
+    return launch_combine(ctx, loop_shaped ? ws.att_chunk_prefix : ws.cmp_chunk_prefix, layer_begin, layer_end, out, lse, st);
 }
 
 }  // namespace kvtrim

@@ -400,7 +400,6 @@ kvtrim_status kvtrim_compact_attn_inplace(kvtrim_ctx* ctx, kvtrim_cache* c, cons
     if (layer_begin < 0 || layer_end > ctx->cfg.n_layers || layer_begin >= layer_end)
         return invalid(ctx, "empty or out-of-range layer range");
     if (!(softmax_scale == softmax_scale)) return invalid(ctx, "softmax_scale is NaN");
-    if (ctx->shape.group > 6) return invalid(ctx, "the in-place path serves groups of at most 6 query heads per KV head");
     if (c->cap_entries / CMP_CHUNK + ctx->shape.nseg > ctx->ws.max_att_chunks)
         return invalid(ctx, "cache too large for the in-place path (more than 524288 chunks of 128 entries)");
     return launch_compact_attn_inplace(ctx, view_mut_of(c), keep, kept, view_mut_of(spare), (const uint16_t*)q, layer_begin,

@@ -166,6 +166,8 @@ void launch_cmp_scan(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, con
                      const CacheViewMut& dst, int32_t reserve, hipStream_t);
 bool launch_attn_fused(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const CacheViewMut& dst, const uint16_t* q,
                        int32_t layer_begin, int32_t layer_end, float scale, hipStream_t st);
+bool launch_attn_fused_inplace(kvtrim_ctx*, const CacheViewMut& c, const uint8_t* keep, const CacheViewMut& stage,
+                               const uint16_t* q, int32_t layer_begin, int32_t layer_end, float scale, hipStream_t st);
 kvtrim_status launch_combine(kvtrim_ctx*, const int32_t* chunk_prefix, int32_t layer_begin, int32_t layer_end,
                              float* out, float* lse, hipStream_t);
 void launch_cmp_scan_inplace(kvtrim_ctx*, const CacheViewMut& c, const uint8_t* keep, const int32_t* kept, hipStream_t);
