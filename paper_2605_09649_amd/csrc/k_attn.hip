@@ -293,8 +293,9 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_fused(CacheView src, const 
     constexpr int VPR = D / E;                                    // vectors per row = 16
     __shared__ float s_m[NSTREAM][G], s_l[NSTREAM][G];
     __shared__ float s_o[NSTREAM][G][D];
-    __shared__ int s_list[FUSE_RUN];
-    __shared__ int s_wcnt[FUSE_RUN / 64];
+    constexpr int RUN = INPLACE ? FUSE_RUN_INPLACE : FUSE_RUN;    // source entries per block
+    __shared__ int s_list[RUN];
+    __shared__ int s_wcnt[RUN / 64];
 
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     if (__hip_atomic_load(ws.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
@@ -307,21 +308,32 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_fused(CacheView src, const 
     const int cmp_ch = ws.cmp_chunk_prefix[seg] + (int)((sbase - src.seg_start[seg]) / CMP_CHUNK);
     const int64_t dflag = ws.cmp_chunk_dst[cmp_ch];
     const int64_t dbase = dflag & ~CMP_DST_FULL;                  // first destination entry of its survivors
-    // INPLACE: the run loses nothing (both of its chunks are marked) ...
-    const bool ident = INPLACE && (dflag & CMP_DST_FULL) != 0 &&
-                       (cd.n <= CMP_CHUNK || (ws.cmp_chunk_dst[cmp_ch + 1] & CMP_DST_FULL) != 0);
+    // INPLACE: the run loses nothing (all of its chunks are marked) ...
+    bool ident = INPLACE;
+    if (INPLACE) {
+#pragma unroll
+        for (int c = 0; c < RUN / CMP_CHUNK; ++c)
+            if (c * CMP_CHUNK < cd.n) ident = ident && (ws.cmp_chunk_dst[cmp_ch + c] & CMP_DST_FULL) != 0;
+    }
     const bool moves = !INPLACE || !(ident && dbase == sbase);    // ... and stays where it is; uniform over the block
 
     // survivors of the run, in order: passes of 256 entries, ranks from ballots and wavefront counts
-    constexpr int NPASS = FUSE_RUN / ATT_THREADS;
-    static_assert(!INPLACE || NPASS == 1, "the in-place instance keeps one entry's metadata per thread");
+    constexpr int NPASS = RUN / ATT_THREADS;
     int cnt = 0;
-    float md_lb = 0.f, md_lt = 0.f;
-    int md_pos = 0, md_rank = tid;
-    bool md_mine = false;
+    float md_lb[NPASS], md_lt[NPASS];                             // INPLACE: the metadata of the thread's entries
+    int md_pos[NPASS], md_rank[NPASS];
+    bool md_mine[NPASS];
+#pragma unroll
+    for (int h = 0; h < NPASS; ++h) {
+        md_lb[h] = md_lt[h] = 0.f;
+        md_pos[h] = 0;
+        md_rank[h] = h * ATT_THREADS + tid;
+        md_mine[h] = false;
+    }
     if (ident) {
         cnt = cd.n;
-        md_mine = moves && tid < cd.n;
+#pragma unroll
+        for (int h = 0; h < NPASS; ++h) md_mine[h] = moves && h * ATT_THREADS + tid < cd.n;
     } else {
         bool flag[NPASS];
         int rank[NPASS];
@@ -335,7 +347,7 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_fused(CacheView src, const 
         }
         __syncthreads();
 #pragma unroll
-        for (int w = 0; w < FUSE_RUN / 64; ++w) {
+        for (int w = 0; w < RUN / 64; ++w) {
             const int c = s_wcnt[w];
 #pragma unroll
             for (int h = 0; h < NPASS; ++h)
@@ -348,8 +360,8 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_fused(CacheView src, const 
                 const int i = h * ATT_THREADS + tid;
                 s_list[rank[h]] = i;
                 if (INPLACE) {
-                    md_mine = true;
-                    md_rank = rank[h];
+                    md_mine[h] = true;
+                    md_rank[h] = rank[h];
                 } else {
                     dst.log_beta[dbase + rank[h]] = src.log_beta[sbase + i];
                     if (src.log_tail) dst.log_tail[dbase + rank[h]] = src.log_tail[sbase + i];
@@ -360,20 +372,27 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_fused(CacheView src, const 
     }
     if (INPLACE) {
         // the metadata of every entry of the run is in registers before any of it is overwritten
-        if (md_mine) {
-            md_lb = src.log_beta[sbase + tid];
-            if (src.log_tail) md_lt = src.log_tail[sbase + tid];
-            md_pos = src.pos[sbase + tid];
+#pragma unroll
+        for (int h = 0; h < NPASS; ++h) {
+            const int i = h * ATT_THREADS + tid;
+            if (md_mine[h]) {
+                md_lb[h] = src.log_beta[sbase + i];
+                if (src.log_tail) md_lt[h] = src.log_tail[sbase + i];
+                md_pos[h] = src.pos[sbase + i];
+            }
         }
         if (moves) {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
-            const int64_t de = dbase + md_rank;
-            if (md_mine && de != sbase + tid) {
-                const CacheViewMut& t = de >= sbase ? dst : stage;
-                t.log_beta[de] = md_lb;
-                if (src.log_tail) t.log_tail[de] = md_lt;
-                t.pos[de] = md_pos;
+#pragma unroll
+            for (int h = 0; h < NPASS; ++h) {
+                const int64_t de = dbase + md_rank[h];
+                if (md_mine[h] && de != sbase + h * ATT_THREADS + tid) {
+                    const CacheViewMut& t = de >= sbase ? dst : stage;
+                    t.log_beta[de] = md_lb[h];
+                    if (src.log_tail) t.log_tail[de] = md_lt[h];
+                    t.pos[de] = md_pos[h];
+                }
             }
         }
     } else {
@@ -722,13 +741,13 @@ bool launch_attn_fused_inplace(kvtrim_ctx* ctx, const CacheViewMut& c, const uin
                                const uint16_t* q, int32_t layer_begin, int32_t layer_end, float scale, hipStream_t st) {
     const Shape& sh = ctx->shape;
     const Workspace& ws = ctx->ws;
-    const int64_t max_chunks = c.cap / FUSE_RUN + sh.nseg;
+    const int64_t max_chunks = c.cap / FUSE_RUN_INPLACE + sh.nseg;
     const float scale_log2 = scale * 1.4426950408889634f;
     CacheView src;
     src.k = c.k; src.v = c.v; src.log_beta = c.log_beta; src.pos = c.pos;
     src.seg_start = c.seg_start; src.seg_len = c.seg_len; src.cap = c.cap; src.log_tail = c.log_tail;
     { ProfScope prof(ctx, K_ATT_PLAN, st);
-      hipLaunchKernelGGL(k_att_plan, dim3(1), dim3(1024), 0, st, src, sh, ws, FUSE_RUN, 0, sh.n_layers, max_chunks); }
+      hipLaunchKernelGGL(k_att_plan, dim3(1), dim3(1024), 0, st, src, sh, ws, FUSE_RUN_INPLACE, 0, sh.n_layers, max_chunks); }
     ProfScope prof(ctx, K_ATT_FUSED, st);
     const dim3 grid((unsigned)max_chunks), block(ATT_THREADS);
 #define KVTRIM_CASE(d, g) \

@@ -483,7 +483,7 @@ kvtrim_status launch_compact_attn_inplace(kvtrim_ctx* ctx, const CacheViewMut& c
     {
         ProfScope prof(ctx, K_CMP_UNSTAGE, st);
         const dim3 grid((unsigned)((max_chunks + UNS_THREADS / 64 - 1) / (UNS_THREADS / 64)));
-        const int run_chunks = loop_shaped ? 2 : 1;
+        const int run_chunks = loop_shaped ? FUSE_RUN_INPLACE / CMP_CHUNK : 1;
         if (sh.head_dim == 128)
             hipLaunchKernelGGL(k_cmp_unstage<128>, grid, dim3(UNS_THREADS), 0, st, c, stage, kept, sh, ws, run_chunks);
         else
