@@ -701,17 +701,15 @@ kvtrim_status launch_attn(kvtrim_ctx* ctx, const CacheView& c, const uint16_t* q
     return launch_combine(ctx, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, st);
 }
 
-// The loop-shaped fused pass for G > 4 (k_att_fused): the compaction tables must be in the workspace
-// (launch_cmp_scan); builds the run table over the source, moves every segment, attends the layer range.
+// The loop-shaped fused pass for G > 4 (k_att_fused): the compaction tables and the run table must be in the
+// workspace (launch_cmp_scan_aligned with run = FUSE_RUN); moves every segment, attends the layer range.
 // Returns false when the group size has no instance.
 bool launch_attn_fused(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const CacheViewMut& dst,
                        const uint16_t* q, int32_t layer_begin, int32_t layer_end, float scale, hipStream_t st) {
     const Shape& sh = ctx->shape;
     const Workspace& ws = ctx->ws;
-    const int64_t max_chunks = src.cap / FUSE_RUN + sh.nseg;
+    const int64_t max_chunks = src.cap / FUSE_RUN + sh.nseg;      // the run table comes from the compaction scan
     const float scale_log2 = scale * 1.4426950408889634f;
-    { ProfScope prof(ctx, K_ATT_PLAN, st);
-      hipLaunchKernelGGL(k_att_plan, dim3(1), dim3(1024), 0, st, src, sh, ws, FUSE_RUN, 0, sh.n_layers, max_chunks); }
     ProfScope prof(ctx, K_ATT_FUSED, st);
     const dim3 grid((unsigned)max_chunks), block(ATT_THREADS);
 #define KVTRIM_CASE(d, g) \
@@ -746,9 +744,7 @@ bool launch_attn_fused_inplace(kvtrim_ctx* ctx, const CacheViewMut& c, const uin
     CacheView src;
     src.k = c.k; src.v = c.v; src.log_beta = c.log_beta; src.pos = c.pos;
     src.seg_start = c.seg_start; src.seg_len = c.seg_len; src.cap = c.cap; src.log_tail = c.log_tail;
-    { ProfScope prof(ctx, K_ATT_PLAN, st);
-      hipLaunchKernelGGL(k_att_plan, dim3(1), dim3(1024), 0, st, src, sh, ws, FUSE_RUN_INPLACE, 0, sh.n_layers, max_chunks); }
-    ProfScope prof(ctx, K_ATT_FUSED, st);
+    ProfScope prof(ctx, K_ATT_FUSED, st);                         // (the run table comes from the compaction scan)
     const dim3 grid((unsigned)max_chunks), block(ATT_THREADS);
 #define KVTRIM_CASE(d, g) \
     case g: hipLaunchKernelGGL((k_att_fused<d, g, true>), grid, block, 0, st, src, keep, c, stage, q, sh, ws, scale_log2, layer_begin, layer_end); return true;

@@ -41,16 +41,16 @@ __device__ __forceinline__ void block_sum_n(int64_t (&v)[N], int64_t* lds /* [16
 // they are and there is no capacity to check.
 __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_prefix(CacheView src, const int32_t* __restrict__ kept,
                                                              CacheViewMut dst, int reserve, int align, Shape sh,
-                                                             Workspace ws, int inplace) {
+                                                             Workspace ws, int inplace, int run) {
     __shared__ int64_t lds64[17];
     __shared__ int s_bad_layout, s_bad_kept;
     const int tid = threadIdx.x, nseg = sh.nseg;
     if (tid == 0) s_bad_layout = s_bad_kept = 0;
     __syncthreads();
-    int64_t chunks = 0, entries = 0;
+    int64_t chunks = 0, entries = 0, runs = 0;
     for (int base = 0; base < nseg; base += SCAN_THREADS) {
         const int i = base + tid;
-        int64_t nch = 0, need = 0;
+        int64_t nch = 0, need = 0, nrun = 0;
         if (i < nseg) {
             const int len = src.seg_len[i];
             const int64_t st = src.seg_start[i];
@@ -59,6 +59,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_prefix(CacheView src, cons
             if (kp < 0 || kp > len) s_bad_kept = 1;
             nch = len > 0 ? ((int64_t)len + CMP_CHUNK - 1) / CMP_CHUNK : 0;
             need = ((int64_t)kp + reserve + align - 1) / align * align;
+            nrun = run > 0 && len > 0 ? ((int64_t)len + run - 1) / run : 0;
         }
         int64_t tot_c, tot_e;
         const int64_t ex_c = block_excl_scan<int64_t>(nch, lds64, &tot_c);
@@ -69,38 +70,50 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_prefix(CacheView src, cons
         }
         chunks += tot_c;
         entries += tot_e;
+        if (run > 0) {                                            // uniform over the block
+            int64_t tot_r;
+            const int64_t ex_r = block_excl_scan<int64_t>(nrun, lds64, &tot_r);
+            if (i < nseg) ws.att_chunk_prefix[i] = (int32_t)min(runs + ex_r, (int64_t)0x7fffffff);
+            runs += tot_r;
+        }
     }
     __syncthreads();
-    const bool bad_layout = s_bad_layout || chunks > ws.max_cmp_chunks, bad_kept = s_bad_kept != 0;
+    const bool bad_layout = s_bad_layout || chunks > ws.max_cmp_chunks || runs > ws.max_att_chunks, bad_kept = s_bad_kept != 0;
     if (tid == 0) {
         if (bad_layout || bad_kept || (!inplace && entries > dst.cap)) {
             atomicOr(ws.err, bad_layout ? ERR_LAYOUT : (bad_kept ? ERR_MISMATCH : ERR_CAP));
             ws.cmp_chunk_prefix[nseg] = 0;
+            if (run > 0) ws.att_chunk_prefix[nseg] = 0;
         } else {
             ws.cmp_chunk_prefix[nseg] = (int32_t)chunks;
+            if (run > 0) ws.att_chunk_prefix[nseg] = (int32_t)runs;
         }
     }
 }
 
 // PRE: k_cmp_prefix has run (segment prefixes and the checks over all segments are done).
+// run > 0: the table of `run`-entry runs of all segments (ws.att_chunk_prefix / ws.att_desc, what k_att_plan builds
+// for the whole layer range) is written as well, for the loop-shaped fused kernel that follows.
 template <bool PRE>
 __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const uint8_t* __restrict__ keep,
                                                            const int32_t* __restrict__ kept, CacheViewMut dst,
-                                                           int reserve, int align, Shape sh, Workspace ws, int inplace) {
+                                                           int reserve, int align, Shape sh, Workspace ws, int inplace,
+                                                           int run) {
     __shared__ int64_t lds64[17];
-    __shared__ int64_t lds_n[16 * 6];
+    __shared__ int64_t lds_n[16 * 8];
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int g = blockIdx.x;
     const int nseg = sh.nseg;
 
-    int64_t chunks_before, dst_before;
+    int64_t chunks_before, dst_before, runs_before = 0;
     if (PRE) {
         if (__hip_atomic_load(ws.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
         chunks_before = ws.cmp_chunk_prefix[g];
         dst_before = dst.seg_start[g];
+        if (run > 0) runs_before = ws.att_chunk_prefix[g];
     } else {
         // chunks and destination entries of the segments before g, and the totals
-        int64_t acc[6] = {0, 0, 0, 0, 0, 0};   // chunks_before, dst_before, dst_total, chunks_total, bad_layout, bad_kept
+        int64_t acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // chunks_before, dst_before, dst_total, chunks_total, bad_layout, bad_kept, runs_before, runs_total
         for (int i = tid; i < nseg; i += SCAN_THREADS) {
             const int len = src.seg_len[i];
             const int64_t st = src.seg_start[i];
@@ -109,23 +122,30 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const 
             acc[5] |= (kp < 0 || kp > len);
             const int64_t nch = len > 0 ? ((int64_t)len + CMP_CHUNK - 1) / CMP_CHUNK : 0;
             const int64_t need = ((int64_t)kp + reserve + align - 1) / align * align;   // align = 1 unless pages are built
+            const int64_t nrun = run > 0 && len > 0 ? ((int64_t)len + run - 1) / run : 0;
             acc[3] += nch;
             acc[2] += need;
+            acc[7] += nrun;
             if (i < g) {
                 acc[0] += nch;
                 acc[1] += need;
+                acc[6] += nrun;
             }
         }
-        block_sum_n<6>(acc, lds_n);
+        block_sum_n<8>(acc, lds_n);
         chunks_before = acc[0];
         dst_before = acc[1];
+        runs_before = acc[6];
         const int64_t dst_total = acc[2], chunks_total = acc[3];
-        const bool bad_layout = acc[4] != 0 || chunks_total > ws.max_cmp_chunks, bad_kept = acc[5] != 0;
+        const bool bad_layout = acc[4] != 0 || chunks_total > ws.max_cmp_chunks || acc[7] > ws.max_att_chunks, bad_kept = acc[5] != 0;
         if (inplace) dst_before = src.seg_start[g];               // the segment keeps its place
         if (bad_layout || bad_kept || (!inplace && dst_total > dst.cap)) {   // every block takes the same decision
             if (tid == 0) {
                 atomicOr(ws.err, bad_layout ? ERR_LAYOUT : (bad_kept ? ERR_MISMATCH : ERR_CAP));
-                if (g == 0) ws.cmp_chunk_prefix[nseg] = 0;
+                if (g == 0) {
+                    ws.cmp_chunk_prefix[nseg] = 0;
+                    if (run > 0) ws.att_chunk_prefix[nseg] = 0;
+                }
             }
             return;
         }
@@ -136,6 +156,20 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const 
     const int nch = len > 0 ? (len + CMP_CHUNK - 1) / CMP_CHUNK : 0;
     const uint8_t* kp = keep + start;
     const int cbase = (int)chunks_before;
+    if (run > 0) {                                                // the segment's runs, for the loop-shaped fused kernel
+        const int nrun = len > 0 ? (int)(((int64_t)len + run - 1) / run) : 0;
+        for (int u = tid; u < nrun; u += SCAN_THREADS) {
+            ChunkDesc d;
+            d.first = start + (int64_t)u * run;
+            d.n = min(run, len - u * run);
+            d.seg = g;
+            ws.att_desc[runs_before + u] = d;
+        }
+        if (tid == 0 && !PRE) {
+            ws.att_chunk_prefix[g] = (int32_t)runs_before;
+            if (g == nseg - 1) ws.att_chunk_prefix[nseg] = (int32_t)(runs_before + nrun);
+        }
+    }
 
     // phase 1: survivors per chunk (one wavefront per chunk, two coalesced byte loads per lane)
     for (int ch = wave; ch < nch; ch += SCAN_THREADS / 64) {
@@ -275,38 +309,39 @@ __global__ __launch_bounds__(CMP_THREADS) void k_cmp_copy(CacheView src, const u
 }
 
 void launch_cmp_scan_aligned(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const int32_t* kept,
-                             const CacheViewMut& dst, int32_t reserve, int32_t align, hipStream_t st) {
+                             const CacheViewMut& dst, int32_t reserve, int32_t align, int32_t run, hipStream_t st) {
     ProfScope prof(ctx, K_CMP_SCAN, st);
     if (ctx->shape.nseg > 1024) {                                 // see k_cmp_prefix
-        hipLaunchKernelGGL(k_cmp_prefix, dim3(1), dim3(SCAN_THREADS), 0, st, src, kept, dst, reserve, align, ctx->shape, ctx->ws, 0);
+        hipLaunchKernelGGL(k_cmp_prefix, dim3(1), dim3(SCAN_THREADS), 0, st, src, kept, dst, reserve, align, ctx->shape, ctx->ws, 0, run);
         hipLaunchKernelGGL(k_cmp_scan<true>, dim3(ctx->shape.nseg), dim3(SCAN_THREADS), 0, st, src, keep, kept, dst, reserve,
-                           align, ctx->shape, ctx->ws, 0);
+                           align, ctx->shape, ctx->ws, 0, run);
     } else {
         hipLaunchKernelGGL(k_cmp_scan<false>, dim3(ctx->shape.nseg), dim3(SCAN_THREADS), 0, st, src, keep, kept, dst, reserve,
-                           align, ctx->shape, ctx->ws, 0);
+                           align, ctx->shape, ctx->ws, 0, run);
     }
 }
 
 // The tables for a compaction inside the cache itself: every segment keeps its start, chunk ch's survivors go to
 // ws.cmp_chunk_dst[ch] = seg_start + survivors of the segment's earlier chunks; nothing of the cache is written.
-void launch_cmp_scan_inplace(kvtrim_ctx* ctx, const CacheViewMut& c, const uint8_t* keep, const int32_t* kept, hipStream_t st) {
+void launch_cmp_scan_inplace(kvtrim_ctx* ctx, const CacheViewMut& c, const uint8_t* keep, const int32_t* kept, int32_t run,
+                             hipStream_t st) {
     ProfScope prof(ctx, K_CMP_SCAN, st);
     CacheView src;
     src.k = c.k; src.v = c.v; src.log_beta = c.log_beta; src.pos = c.pos;
     src.seg_start = c.seg_start; src.seg_len = c.seg_len; src.cap = c.cap; src.log_tail = c.log_tail;
     if (ctx->shape.nseg > 1024) {
-        hipLaunchKernelGGL(k_cmp_prefix, dim3(1), dim3(SCAN_THREADS), 0, st, src, kept, c, 0, 1, ctx->shape, ctx->ws, 1);
+        hipLaunchKernelGGL(k_cmp_prefix, dim3(1), dim3(SCAN_THREADS), 0, st, src, kept, c, 0, 1, ctx->shape, ctx->ws, 1, run);
         hipLaunchKernelGGL(k_cmp_scan<true>, dim3(ctx->shape.nseg), dim3(SCAN_THREADS), 0, st, src, keep, kept, c, 0, 1,
-                           ctx->shape, ctx->ws, 1);
+                           ctx->shape, ctx->ws, 1, run);
     } else {
         hipLaunchKernelGGL(k_cmp_scan<false>, dim3(ctx->shape.nseg), dim3(SCAN_THREADS), 0, st, src, keep, kept, c, 0, 1,
-                           ctx->shape, ctx->ws, 1);
+                           ctx->shape, ctx->ws, 1, run);
     }
 }
 
 void launch_cmp_scan(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const int32_t* kept,
                      const CacheViewMut& dst, int32_t reserve, hipStream_t st) {
-    launch_cmp_scan_aligned(ctx, src, keep, kept, dst, reserve, 1, st);
+    launch_cmp_scan_aligned(ctx, src, keep, kept, dst, reserve, 1, 0, st);
 }
 
 kvtrim_status launch_compact(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const int32_t* kept,

@@ -426,7 +426,7 @@ kvtrim_status launch_compact_attn(kvtrim_ctx* ctx, const CacheView& src, const u
         max_chunks <= ws.max_cmp_chunks) {
         // Large groups of query heads: the loop-shaped fused kernel (the split-K attention kernel reading the source
         // through the survivor lists and writing the rows out as well), whose cost hardly depends on G.
-        launch_cmp_scan(ctx, src, keep, kept, dst, reserve, st);
+        launch_cmp_scan_aligned(ctx, src, keep, kept, dst, reserve, 1, FUSE_RUN_ENTRIES, st);
         if (!launch_attn_fused(ctx, src, keep, dst, q, layer_begin, layer_end, scale, st)) return KVTRIM_EINVAL;
         return launch_combine(ctx, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, st);
     }
@@ -465,7 +465,7 @@ kvtrim_status launch_compact_attn_inplace(kvtrim_ctx* ctx, const CacheViewMut& c
     CacheView src;
     src.k = c.k; src.v = c.v; src.log_beta = c.log_beta; src.pos = c.pos;
     src.seg_start = c.seg_start; src.seg_len = c.seg_len; src.cap = c.cap; src.log_tail = c.log_tail;
-    launch_cmp_scan_inplace(ctx, c, keep, kept, st);
+    launch_cmp_scan_inplace(ctx, c, keep, kept, sh.group > 6 ? FUSE_RUN_INPLACE : 0, st);
     // up to six query heads per KV head: the one-shot kernel (long-context workload, G = 4: 0.368 ms per step against
     // 0.382 with the loop-shaped one); seven and eight: the loop-shaped kernel, as out of place
     const bool loop_shaped = sh.group > 6;

@@ -159,8 +159,10 @@ kvtrim_status launch_attn_paged(kvtrim_ctx*, const CacheView& pool, const int32_
                                 int max_chunks,
                                 int32_t layer_begin, int32_t layer_end, float scale, float* out, float* lse,
                                 hipStream_t);
+// run > 0: also writes the table of `run`-entry runs of all segments that the loop-shaped fused kernel reads
+// (ws.att_chunk_prefix / ws.att_desc), so that no separate plan kernel is needed.
 void launch_cmp_scan_aligned(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const int32_t* kept,
-                             const CacheViewMut& dst, int32_t reserve, int32_t align, hipStream_t);
+                             const CacheViewMut& dst, int32_t reserve, int32_t align, int32_t run, hipStream_t);
 kvtrim_status launch_cmp_copy(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const CacheViewMut& dst,
                               hipStream_t);
 kvtrim_status launch_occupancy(kvtrim_ctx*, const CacheView&, const int32_t* now, double* occ, hipStream_t);
@@ -172,7 +174,7 @@ bool launch_attn_fused_inplace(kvtrim_ctx*, const CacheViewMut& c, const uint8_t
                                const uint16_t* q, int32_t layer_begin, int32_t layer_end, float scale, hipStream_t st);
 kvtrim_status launch_combine(kvtrim_ctx*, const int32_t* chunk_prefix, int32_t layer_begin, int32_t layer_end,
                              float* out, float* lse, hipStream_t);
-void launch_cmp_scan_inplace(kvtrim_ctx*, const CacheViewMut& c, const uint8_t* keep, const int32_t* kept, hipStream_t);
+void launch_cmp_scan_inplace(kvtrim_ctx*, const CacheViewMut& c, const uint8_t* keep, const int32_t* kept, int32_t run, hipStream_t);
 // Stages 3 + 4 inside the cache itself (every segment keeps its start); `stage` lends its row and metadata arrays.
 kvtrim_status launch_compact_attn_inplace(kvtrim_ctx*, const CacheViewMut& c, const uint8_t* keep, const int32_t* kept,
                                           const CacheViewMut& stage, const uint16_t* q, int32_t layer_begin,
