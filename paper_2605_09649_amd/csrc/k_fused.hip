@@ -405,6 +405,119 @@ __global__ __launch_bounds__(UNS_THREADS) void k_cmp_unstage(CacheViewMut c, Cac
     }
 }
 
+// Stage 3 alone inside the cache: k_cmp_attn<.., INPLACE> without the attention.  A chunk that loses nothing and
+// stays where it is - almost every chunk of a decode step - ends after reading its descriptor, so the kernel
+// touches only the rows behind an eviction.
+template <int D>
+__global__ __launch_bounds__(CMP_THREADS) void k_cmp_move_inplace(CacheViewMut c, const uint8_t* __restrict__ keep,
+                                                                  CacheViewMut stage, Shape sh, Workspace ws) {
+    constexpr int VPR = D / 8;                    // 16-byte vectors per row
+    constexpr int RPI = 64 / VPR;                 // rows moved by one wavefront instruction
+    constexpr int BATCH = CMP_WAVE_ROWS / RPI;    // instructions per wavefront: 4 (D=128) or 2 (D=64)
+    __shared__ int wave_cnt[CMP_CHUNK / 64];
+    __shared__ int list[CMP_CHUNK];
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    const int ch = blockIdx.x;
+    const ChunkDesc cd = ws.cmp_desc[ch];
+    const int64_t dflag = ws.cmp_chunk_dst[ch];
+    if (__hip_atomic_load(ws.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
+    if (ch >= ws.cmp_chunk_prefix[sh.nseg]) return;
+    const int64_t sbase = cd.first, dbase = dflag & ~CMP_DST_FULL;
+    const bool full = (dflag & CMP_DST_FULL) != 0;
+    if (full && dbase == sbase) return;                           // nothing of this chunk moves
+    int cnt = cd.n, rank = tid;
+    bool mine = tid < cd.n;                                       // this thread carries an entry's metadata
+    if (!full) {
+        rank = 0;
+        mine = false;
+        if (tid < CMP_CHUNK) {
+            mine = tid < cd.n && keep[sbase + tid] != 0;
+            const uint64_t mask = __ballot(mine);
+            rank = mbcnt(mask);
+            if (lane == 0) wave_cnt[wave] = __popcll(mask);
+        }
+        __syncthreads();
+        cnt = 0;
+#pragma unroll
+        for (int w = 0; w < CMP_CHUNK / 64; ++w) {
+            if (w < wave && tid < CMP_CHUNK) rank += wave_cnt[w];
+            cnt += wave_cnt[w];
+        }
+        if (mine) list[rank] = tid;
+        __syncthreads();
+    }
+    float md_lb = 0.f, md_lt = 0.f;
+    int md_pos = 0;
+    if (mine) {
+        md_lb = c.log_beta[sbase + tid];
+        if (c.log_tail) md_lt = c.log_tail[sbase + tid];
+        md_pos = c.pos[sbase + tid];
+    }
+    const int r0 = wave * CMP_WAVE_ROWS;                          // this wavefront's rows of the survivor list
+    const int sub = lane / VPR, col = lane % VPR;
+    uint4 kk[BATCH], vv[BATCH];
+    int srow[BATCH];
+    if (r0 < cnt) {
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const int r = min(r0 + u * RPI + sub, cnt - 1);       // clamped: loads stay on live rows
+            srow[u] = full ? r : list[r];
+            const int64_t se = (sbase + srow[u]) * VPR + col;
+            kk[u] = reinterpret_cast<const uint4*>(c.k)[se];
+            vv[u] = reinterpret_cast<const uint4*>(c.v)[se];
+        }
+    }
+    // every wavefront of the block holds its rows and metadata in registers before any of them overwrites an entry
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (mine) {
+        const int64_t de = dbase + rank;
+        if (de != sbase + tid) {
+            const CacheViewMut& t = de >= sbase ? c : stage;
+            t.log_beta[de] = md_lb;
+            if (c.log_tail) t.log_tail[de] = md_lt;
+            t.pos[de] = md_pos;
+        }
+    }
+    if (r0 < cnt) {
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const int r = r0 + u * RPI + sub;
+            if (r < cnt && dbase + r != sbase + srow[u]) {
+                const int64_t de = (dbase + r) * VPR + col;
+                const bool own = dbase + r >= sbase;
+                reinterpret_cast<uint4*>(own ? c.k : stage.k)[de] = kk[u];
+                reinterpret_cast<uint4*>(own ? c.v : stage.v)[de] = vv[u];
+            }
+        }
+    }
+}
+
+kvtrim_status launch_compact_inplace(kvtrim_ctx* ctx, const CacheViewMut& c, const uint8_t* keep, const int32_t* kept,
+                                     const CacheViewMut& stage, hipStream_t st) {
+    const Shape& sh = ctx->shape;
+    const Workspace& ws = ctx->ws;
+    const int64_t max_chunks = c.cap / CMP_CHUNK + sh.nseg;
+    launch_cmp_scan_inplace(ctx, c, keep, kept, 0, st);
+    {
+        ProfScope prof(ctx, K_CMP_COPY, st);
+        if (sh.head_dim == 128)
+            hipLaunchKernelGGL(k_cmp_move_inplace<128>, dim3((unsigned)max_chunks), dim3(CMP_THREADS), 0, st, c, keep, stage, sh, ws);
+        else
+            hipLaunchKernelGGL(k_cmp_move_inplace<64>, dim3((unsigned)max_chunks), dim3(CMP_THREADS), 0, st, c, keep, stage, sh, ws);
+    }
+    {
+        ProfScope prof(ctx, K_CMP_UNSTAGE, st);
+        const dim3 grid((unsigned)((max_chunks + UNS_THREADS / 64 - 1) / (UNS_THREADS / 64)));
+        if (sh.head_dim == 128)
+            hipLaunchKernelGGL(k_cmp_unstage<128>, grid, dim3(UNS_THREADS), 0, st, c, stage, kept, sh, ws, 1);
+        else
+            hipLaunchKernelGGL(k_cmp_unstage<64>, grid, dim3(UNS_THREADS), 0, st, c, stage, kept, sh, ws, 1);
+    }
+    KVTRIM_HIP(ctx, hipGetLastError());
+    return KVTRIM_OK;
+}
+
 // Largest group of query heads the one-shot fused kernel is used for (beyond it, the loop-shaped one).
 constexpr int FUSED_ONE_SHOT_MAX_G_128 = 5, FUSED_ONE_SHOT_MAX_G_64 = 4;
 constexpr int FUSE_RUN_ENTRIES = 2 * CMP_CHUNK;                   // source entries per block of the loop-shaped fused kernel

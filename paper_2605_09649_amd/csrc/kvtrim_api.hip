@@ -382,19 +382,33 @@ kvtrim_status kvtrim_compact_attn(kvtrim_ctx* ctx, const kvtrim_cache* src, cons
                                layer_begin, layer_end, softmax_scale, out, lse, (hipStream_t)hip_stream);
 }
 
+// argument checks shared by the two in-place calls; returns NULL when cache, spare, keep and kept are usable
+static const char* inplace_problem(const kvtrim_ctx* ctx, const kvtrim_cache* c, const uint8_t* keep, const int32_t* kept,
+                                   const kvtrim_cache* spare) {
+    if (const char* p = cache_problem(ctx, c, true)) return p;
+    if (!spare || !spare->k || !spare->v || !spare->log_beta || !spare->pos) return "spare or one of its k / v / log_beta / pos arrays is NULL";
+    if ((((uintptr_t)spare->k) | ((uintptr_t)spare->v)) & 15) return "spare k/v not 16-byte aligned";
+    if (spare->cap_entries < c->cap_entries) return "spare holds fewer entries than the cache";
+    if (c->k == spare->k || c->v == spare->v || c->log_beta == spare->log_beta || c->pos == spare->pos)
+        return "the cache and spare share a buffer";
+    if (c->log_tail && (!spare->log_tail || spare->log_tail == c->log_tail))
+        return "the cache carries log_tail: spare needs a log_tail array of its own";
+    if (!keep || !kept) return "keep / kept is NULL";
+    return nullptr;
+}
+
+kvtrim_status kvtrim_compact_inplace(kvtrim_ctx* ctx, kvtrim_cache* c, const uint8_t* keep, const int32_t* kept,
+                                     kvtrim_cache* spare, void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    if (const char* p = inplace_problem(ctx, c, keep, kept, spare)) return invalid(ctx, p);
+    return launch_compact_inplace(ctx, view_mut_of(c), keep, kept, view_mut_of(spare), (hipStream_t)hip_stream);
+}
+
 kvtrim_status kvtrim_compact_attn_inplace(kvtrim_ctx* ctx, kvtrim_cache* c, const uint8_t* keep, const int32_t* kept,
                                           kvtrim_cache* spare, const void* q, int32_t layer_begin, int32_t layer_end,
                                           float softmax_scale, float* out, float* lse, void* hip_stream) {
     if (!ctx) return KVTRIM_EINVAL;
-    if (const char* p = cache_problem(ctx, c, true)) return invalid(ctx, p);
-    if (!spare || !spare->k || !spare->v || !spare->log_beta || !spare->pos) return invalid(ctx, "spare or one of its k / v / log_beta / pos arrays is NULL");
-    if ((((uintptr_t)spare->k) | ((uintptr_t)spare->v)) & 15) return invalid(ctx, "spare k/v not 16-byte aligned");
-    if (spare->cap_entries < c->cap_entries) return invalid(ctx, "spare holds fewer entries than the cache");
-    if (c->k == spare->k || c->v == spare->v || c->log_beta == spare->log_beta || c->pos == spare->pos)
-        return invalid(ctx, "the cache and spare share a buffer");
-    if (c->log_tail && (!spare->log_tail || spare->log_tail == c->log_tail))
-        return invalid(ctx, "the cache carries log_tail: spare needs a log_tail array of its own");
-    if (!keep || !kept) return invalid(ctx, "keep / kept is NULL");
+    if (const char* p = inplace_problem(ctx, c, keep, kept, spare)) return invalid(ctx, p);
     if (!q || !out) return invalid(ctx, "q / out is NULL");
     if (((uintptr_t)q) & 15) return invalid(ctx, "q not 16-byte aligned");
     if (layer_begin < 0 || layer_end > ctx->cfg.n_layers || layer_begin >= layer_end)

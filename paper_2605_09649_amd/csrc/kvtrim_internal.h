@@ -175,6 +175,9 @@ bool launch_attn_fused_inplace(kvtrim_ctx*, const CacheViewMut& c, const uint8_t
 kvtrim_status launch_combine(kvtrim_ctx*, const int32_t* chunk_prefix, int32_t layer_begin, int32_t layer_end,
                              float* out, float* lse, hipStream_t);
 void launch_cmp_scan_inplace(kvtrim_ctx*, const CacheViewMut& c, const uint8_t* keep, const int32_t* kept, int32_t run, hipStream_t);
+// Stage 3 alone inside the cache itself.
+kvtrim_status launch_compact_inplace(kvtrim_ctx*, const CacheViewMut& c, const uint8_t* keep, const int32_t* kept,
+                                     const CacheViewMut& stage, hipStream_t);
 // Stages 3 + 4 inside the cache itself (every segment keeps its start); `stage` lends its row and metadata arrays.
 kvtrim_status launch_compact_attn_inplace(kvtrim_ctx*, const CacheViewMut& c, const uint8_t* keep, const int32_t* kept,
                                           const CacheViewMut& stage, const uint16_t* q, int32_t layer_begin,

@@ -254,10 +254,12 @@ def compare_cache_contents(hc_gpu, hc_ref):
             and np.array_equal(hc_gpu.pos[mg], hc_ref.pos[mr]))
 
 
-def run_steps_inplace_both(w, steps, budget, room, cache_dict, now0, device="cuda:0", horizon=1, rebalance_at=()):
+def run_steps_inplace_both(w, steps, budget, room, cache_dict, now0, device="cuda:0", horizon=1, rebalance_at=(),
+                           two_call=False):
     """The decode loop with stages 3 + 4 done inside the cache (kvtrim_compact_attn_inplace): `cache_dict` must leave
     `room` free slots behind every segment (one is used per step).  At the steps listed in `rebalance_at` the GPU
     side runs the out-of-place fused call instead, into a second cache with `room` free slots per segment again.
+    two_call: stage 3 alone in place (kvtrim_compact_inplace), then kvtrim_decode_attn on the same cache.
     The oracle runs its four stages; scores, mask, counts, threshold, segment contents and attention are compared."""
     cache_dict = ki.with_horizon(cache_dict, horizon)
     hc = host_cache(w, cache_dict)
@@ -297,6 +299,9 @@ def run_steps_inplace_both(w, steps, budget, room, cache_dict, now0, device="cud
         if step in rebalance_at:
             kv.kvtrim_compact_attn(ctx, cur, keep, kept, other, room, d["q"], 0, w.n_layers, scale, out, lse)
             cur, other = other, cur
+        elif two_call:
+            kv.kvtrim_compact_inplace(ctx, cur, keep, kept, other)
+            kv.kvtrim_decode_attn(ctx, cur, d["q"], 0, w.n_layers, scale, out, lse)
         else:
             kv.kvtrim_compact_attn_inplace(ctx, cur, keep, kept, other, d["q"], 0, w.n_layers, scale, out, lse)
         res = {"status": kv.kvtrim_poll_error(ctx), "in_place": step not in rebalance_at}

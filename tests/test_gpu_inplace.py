@@ -48,6 +48,22 @@ def test_in_place_with_a_lookahead_horizon(horizon):
     check(run_steps_inplace_both(w, 4, [sum(seg_len) - 9], 4, c, now.numpy(), device=DEV, horizon=horizon))
 
 
+@pytest.mark.parametrize("G,D", [(4, 128), (3, 64), (8, 128)])
+def test_stage_three_alone_in_place(G, D):
+    # kvtrim_compact_inplace followed by the stand-alone attention on the same cache
+    w = wl(2, 2, 3, G, D)
+    rng = np.random.default_rng(G + D)
+    seg_len = rng.integers(1, 1500, w.nseg)
+    seg_len[1] = 0
+    seg_len[9] = 2 * 128
+    per_seq = [int(seg_len[:6].sum()), int(seg_len[6:].sum())]
+    c, now = ki.ragged_cache(w, seg_len, reserve=5, salt=G)
+    check(run_steps_inplace_both(w, 5, [per_seq[0] - 5, per_seq[1] // 2], 5, c, now.numpy(), device=DEV, two_call=True,
+                                 rebalance_at=(3,)))
+    c, now = ki.ragged_cache(w, seg_len, reserve=2, salt=G + 1)
+    check(run_steps_inplace_both(w, 2, [10 ** 6, 0], 2, c, now.numpy(), device=DEV, two_call=True))
+
+
 def test_in_place_edge_budgets():
     # budget 0 empties every segment, a budget above the count moves nothing, ties everywhere (quantised log beta)
     w = wl(2, 1, 2, 2, 64)
