@@ -23,7 +23,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 CPU_STEPS = 16                 # steps the CPU oracle replays after the timed region (a few seconds of host work)
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs, scaled by a plain copy kernel; None until measured for this workload.
-MEASURED_TRAFFIC = {("long", "k_cmp_attn"): 1.1011e9 + 1.1262e9, ("long", "k_cmp_copy"): None,
+MEASURED_TRAFFIC = {("long", "k_cmp_attn"): 1.1011e9 + 1.1259e9, ("long", "k_cmp_copy"): None,
                     ("long-paged", "k_att_partial"): 1.0942e9 + 8.8e6, ("gate-1", "k_gate_hidden"): 136.5e6 + 65.5e3}
 
 
