@@ -117,3 +117,34 @@ def test_in_place_argument_checks():
         kv.kvtrim_compact_attn_inplace(ctx, a, keep, kept, b, q, 1, 1, 0.125, out)
     kv.kvtrim_compact_attn_inplace(ctx, a, keep, kept, b, q, 0, 1, 0.125, out)   # an empty cache is fine
     assert kv.kvtrim_poll_error(ctx) == 0
+
+
+@pytest.mark.parametrize("G", [4, 7])
+def test_in_place_layer_range(G):
+    # a layer range attends only its layers (the other rows of `out` stay as they were) while every segment is
+    # compacted; the attended rows and the cache equal those of a full-range call on a copy of the cache
+    w = wl(1, 3, 2, G, 128)
+    seg_len = [400, 130, 700, 5, 256, 300]
+    c, now = ki.ragged_cache(w, seg_len, reserve=2, salt=11)
+    cap = c["cap"]
+    ctx = kv.Context(1, 3, 2, 2 * G, 128, cap)
+    a, b = kv.Cache.from_dict(c, DEV), kv.Cache.from_dict({k: (v.clone() if torch.is_tensor(v) else v) for k, v in c.items()}, DEV)
+    spare = kv.Cache.empty(w.nseg, 128, cap, DEV)
+    inp = {k: v.to(DEV) for k, v in ki.decode_inputs(w, 0).items()}
+    now_dev = (now + 1).to(DEV)
+    pos = torch.full((w.nseg,), int(now[0]) + 1, dtype=torch.int32, device=DEV)
+    score, keep = torch.zeros(cap, dtype=torch.float32, device=DEV), torch.zeros(cap, dtype=torch.uint8, device=DEV)
+    kept, budget = torch.zeros(w.nseg, dtype=torch.int32, device=DEV), torch.tensor([sum(seg_len) - 40], dtype=torch.int64, device=DEV)
+    outs = []
+    for cache, rng in ((a, (0, 3)), (b, (1, 2))):
+        kv.kvtrim_append(ctx, cache, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos, 1)
+        kv.kvtrim_score(ctx, cache, now_dev, score)
+        kv.kvtrim_select_global(ctx, cache, score, budget, keep, kept)
+        out = torch.full((1, 3, 2 * G, 128), 7.0, dtype=torch.float32, device=DEV)
+        kv.kvtrim_compact_attn_inplace(ctx, cache, keep, kept, spare, inp["q"], rng[0], rng[1], 0.0884, out)
+        assert kv.kvtrim_poll_error(ctx) == 0
+        outs.append(out.cpu())
+    assert torch.equal(outs[1][:, 1], outs[0][:, 1])
+    assert bool((outs[1][:, 0] == 7.0).all()) and bool((outs[1][:, 2] == 7.0).all())
+    from harness import compare_cache_contents, device_cache_to_host
+    assert compare_cache_contents(device_cache_to_host(w, b), device_cache_to_host(w, a))
