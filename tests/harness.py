@@ -255,10 +255,11 @@ def compare_cache_contents(hc_gpu, hc_ref):
 
 
 def run_steps_inplace_both(w, steps, budget, room, cache_dict, now0, device="cuda:0", horizon=1, rebalance_at=(),
-                           two_call=False):
+                           two_call=False, rebalance_room=None):
     """The decode loop with stages 3 + 4 done inside the cache (kvtrim_compact_attn_inplace): `cache_dict` must leave
     `room` free slots behind every segment (one is used per step).  At the steps listed in `rebalance_at` the GPU
-    side runs the out-of-place fused call instead, into a second cache with `room` free slots per segment again.
+    side runs the out-of-place fused call instead, into a second cache with `room` free slots per segment again
+    (`rebalance_room(step)` slots if given: a budget that evicts nothing leaves no space to restore the whole room).
     two_call: stage 3 alone in place (kvtrim_compact_inplace), then kvtrim_decode_attn on the same cache.
     The oracle runs its four stages; scores, mask, counts, threshold, segment contents and attention are compared."""
     cache_dict = ki.with_horizon(cache_dict, horizon)
@@ -287,7 +288,7 @@ def run_steps_inplace_both(w, steps, budget, room, cache_dict, now0, device="cud
                       log_tail_new=None if horizon == 1 else inp["log_tail_new"].numpy())
         score_ref = oracle.score(hc, now)
         keep_ref, kept_ref, thr_ref = oracle.select(hc, score_ref, budget_np)
-        hc_next = oracle.compact(hc, keep_ref, cap, room)
+        hc_next = oracle.compact(hc, keep_ref, cap, 1)             # (the oracle packs its segments; one slot for the next token)
         out_ref, lse_ref = oracle.attend(hc_next, bf16_bits(inp["q"]), scale)
         d = {k: v.to(device) for k, v in inp.items()}
         kv.kvtrim_append(ctx, cur, d["k_new"], d["v_new"], d["log_beta_new"], torch.from_numpy(pos_new).to(device), 1,
@@ -297,7 +298,8 @@ def run_steps_inplace_both(w, steps, budget, room, cache_dict, now0, device="cud
         live_gpu = live_mask(device_cache_to_host(w, cur))         # the GPU cache's own layout, after the append
         score_gpu, keep_gpu = score.cpu().numpy(), keep.cpu().numpy()
         if step in rebalance_at:
-            kv.kvtrim_compact_attn(ctx, cur, keep, kept, other, room, d["q"], 0, w.n_layers, scale, out, lse)
+            kv.kvtrim_compact_attn(ctx, cur, keep, kept, other, room if rebalance_room is None else rebalance_room(step),
+                                   d["q"], 0, w.n_layers, scale, out, lse)
             cur, other = other, cur
         elif two_call:
             kv.kvtrim_compact_inplace(ctx, cur, keep, kept, other)

@@ -6,7 +6,7 @@ import pytest
 import torch
 
 import kvtrim_inputs as ki
-from harness import run_steps_both
+from harness import run_steps_both, run_steps_inplace_both
 from paged_harness import run_paged_both
 
 pytestmark = pytest.mark.gpu
@@ -14,7 +14,7 @@ DEV = "cuda:0"
 ATTN_TOL = 5e-3
 
 
-def random_case(seed):
+def random_case(seed, reserve=1):
     rng = np.random.default_rng(1000 + seed)
     S = int(rng.integers(1, 4))
     L = int(rng.integers(1, 4))
@@ -25,7 +25,7 @@ def random_case(seed):
     hi = int(rng.choice([5, 150, 700, 2600]))
     seg_len = rng.integers(0, hi + 1, w.nseg)
     seg_len[rng.random(w.nseg) < 0.2] = 0
-    c, now = ki.ragged_cache(w, seg_len, reserve=1, salt=seed, pos_stride_max=int(rng.integers(1, 5)))
+    c, now = ki.ragged_cache(w, seg_len, reserve=reserve, salt=seed, pos_stride_max=int(rng.integers(1, 5)))
     if rng.random() < 0.5:                                         # few distinct retention values: ties at the threshold
         g = torch.Generator().manual_seed(seed)
         levels = int(rng.choice([1, 2, 7]))
@@ -54,6 +54,15 @@ def test_random_configuration(seed):
         for i, r in enumerate(res):
             assert r["status"] == 0 and r["score_equal"] and r["keep_equal"] and r["cache_equal"], (seed, fused, i, r)
             assert r["attn_err"] <= ATTN_TOL and r["lse_err"] <= 2e-3 and r["lse_inf_equal"], (seed, fused, i, r)
+    # the same configuration compacted inside the cache (fused for even seeds, stage 3 alone + attention for odd ones),
+    # with an out-of-place step in between where there are at least three steps
+    w2, c2, now2, budgets2 = random_case(seed, reserve=len(budgets) + 1)
+    res = run_steps_inplace_both(w2, len(budgets2), budgets2[0], len(budgets2) + 1, c2, now2.numpy(), device=DEV,
+                                 two_call=bool(seed % 2), rebalance_at=(1,) if len(budgets2) > 2 else (),
+                                 rebalance_room=lambda step: len(budgets2) - step - 1)   # budgets above the count evict nothing
+    for i, r in enumerate(res):
+        assert r["status"] == 0 and r["score_equal"] and r["keep_equal"] and r["cache_equal"], (seed, "in place", i, r)
+        assert r["attn_err"] <= ATTN_TOL and r["lse_err"] <= 2e-3 and r["lse_inf_equal"], (seed, "in place", i, r)
     # every other seed also packs the pages after each eviction from the second step on
     defrag_at = tuple(range(1, len(budgets))) if seed % 2 else ()
     res = run_paged_both(w, budgets, device=DEV, cache_dict=clone(), now0=now.numpy(), defrag_at=defrag_at)
