@@ -18,6 +18,10 @@
 // Each 16-lane row group computes a softmax partial over its 4 rows; the four row groups of
 // a wavefront are merged with lane shuffles, the wavefronts of the block through LDS, and
 // the chunks of a segment by k_att_combine.
+//
+// The same kernel has an instance that compacts INSIDE the cache (segments keep their starts; only the rows
+// behind an eviction move), followed by k_cmp_unstage; k_cmp_move_inplace is that instance without the
+// attention (it is bracketed under the row mover's name, k_cmp_copy, when kernels are timed).
 #include "kvtrim_device.h"
 
 namespace kvtrim {
