@@ -16,7 +16,7 @@ import torch
 import kvtrim_inputs as ki
 import oracle
 import paper_2605_09649_amd as kv
-from harness import attn_error, compare_caches, device_cache_to_host, run_steps_both
+from harness import attn_error, compare_caches, device_cache_to_host, run_steps_both, run_steps_inplace_both
 from helpers import bf16_bits, shape_of
 from paged_harness import PagedHost
 
@@ -37,6 +37,17 @@ def test_llama_32k_whole():
     pre = {k: (v.cpu() if torch.is_tensor(v) else v) for k, v in ki.prefill_cache(w, device=DEV).items()}
     check(run_steps_both(w, steps=3, budget=w.budget, device=DEV, cache_dict=pre, now0=[t - 1 for t in w.prefill],
                          fused=True))
+
+
+@pytest.mark.parametrize("name", ["llama", "vlm"])
+def test_steady_state_in_place_whole(name):
+    # the first eviction goes out of place into a cache with four free slots per segment, the next three steps are
+    # compacted inside it (llama: G = 4, the one-shot kernel's instance; vlm: G = 7, the loop-shaped one)
+    w = ki.workload(name)
+    pre = {k: (v.cpu() if torch.is_tensor(v) else v) for k, v in ki.prefill_cache(w, reserve=4, device=DEV).items()}
+    res = run_steps_inplace_both(w, 4, w.budget, 4, pre, [t - 1 for t in w.prefill], device=DEV, rebalance_at=(0,))
+    assert [r["in_place"] for r in res] == [False, True, True, True]
+    check(res)
 
 
 def test_vlm_two_sequences_whole():
