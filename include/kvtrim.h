@@ -201,17 +201,17 @@ kvtrim_status kvtrim_compact_attn(kvtrim_ctx *ctx, const kvtrim_cache *src, cons
  * reading); its contents afterwards are unspecified, its segment tables are not touched.
  * Served for caches of at most 67 M entries (KVTRIM_EINVAL otherwise).  Device-side errors:
  * KVTRIM_EMISMATCH, KVTRIM_ELAYOUT. */
+kvtrim_status kvtrim_compact_attn_inplace(kvtrim_ctx *ctx, kvtrim_cache *c, const uint8_t *keep,
+                                          const int32_t *kept, kvtrim_cache *spare, const void *q,
+                                          int32_t layer_begin, int32_t layer_end, float softmax_scale,
+                                          float *out, float *lse, void *hip_stream);
+
 /* Stage 3 alone, compacting inside the cache: kvtrim_compact_attn_inplace without the attention
  * (same arguments, same rules for `spare`, any cache size the context allows).  Only the rows
  * behind an eviction are touched, so a decode step's compaction costs a fraction of an
  * out-of-place one; kvtrim_decode_attn can then be called layer by layer on the same cache. */
 kvtrim_status kvtrim_compact_inplace(kvtrim_ctx *ctx, kvtrim_cache *c, const uint8_t *keep, const int32_t *kept,
                                      kvtrim_cache *spare, void *hip_stream);
-
-kvtrim_status kvtrim_compact_attn_inplace(kvtrim_ctx *ctx, kvtrim_cache *c, const uint8_t *keep,
-                                          const int32_t *kept, kvtrim_cache *spare, const void *q,
-                                          int32_t layer_begin, int32_t layer_end, float softmax_scale,
-                                          float *out, float *lse, void *hip_stream);
 
 /* Support - new tokens enter the cache (Sec. 3.2: beta is fixed when the token is
  * first cached).  Appends up to n_new entries to every segment, in order, behind its
