@@ -298,23 +298,18 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_fused(CacheView src, const 
     __shared__ int s_wcnt[RUN / 64];
 
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
-    if (__hip_atomic_load(ws.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
-    const int total = ws.att_chunk_prefix[sh.nseg];
     const int ch = blockIdx.x;
-    if (ch >= total) return;
+    // the run and where its survivors go (both tables come from the compaction scan and cover the whole grid; what
+    // they hold at or beyond the run count is not used), fetched together with the two grid-wide words
     const ChunkDesc cd = ws.att_desc[ch];
+    const int64_t dflag = ws.run_dst[ch];
+    if (__hip_atomic_load(ws.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
+    if (ch >= ws.att_chunk_prefix[sh.nseg]) return;
     const int seg = cd.seg;
     const int64_t sbase = cd.first;                               // first source entry of the run
-    const int cmp_ch = ws.cmp_chunk_prefix[seg] + (int)((sbase - src.seg_start[seg]) / CMP_CHUNK);
-    const int64_t dflag = ws.cmp_chunk_dst[cmp_ch];
     const int64_t dbase = dflag & ~CMP_DST_FULL;                  // first destination entry of its survivors
-    // INPLACE: the run loses nothing (all of its chunks are marked) ...
-    bool ident = INPLACE;
-    if (INPLACE) {
-#pragma unroll
-        for (int c = 0; c < RUN / CMP_CHUNK; ++c)
-            if (c * CMP_CHUNK < cd.n) ident = ident && (ws.cmp_chunk_dst[cmp_ch + c] & CMP_DST_FULL) != 0;
-    }
+    // INPLACE: the run loses nothing (all of its chunks are full) ...
+    const bool ident = INPLACE && (dflag & CMP_DST_FULL) != 0;
     const bool moves = !INPLACE || !(ident && dbase == sbase);    // ... and stays where it is; uniform over the block
 
     // survivors of the run, in order: passes of 256 entries, ranks from ballots and wavefront counts

@@ -202,6 +202,20 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const 
             ws.cmp_chunk_dst[cbase + ch] = (dst_before + running + ex) | (v == min(CMP_CHUNK, len - ch * CMP_CHUNK) ? CMP_DST_FULL : 0);
         running += tot;
     }
+    if (run > 0) {
+        // per run: where its survivors go, and whether every one of its chunks is full (the chunk entries above
+        // were written by other threads of this block)
+        __syncthreads();
+        const int rc = run / CMP_CHUNK;
+        const int nrun = (nch + rc - 1) / rc;
+        for (int u = tid; u < nrun; u += SCAN_THREADS) {
+            const int c0 = cbase + u * rc;
+            int64_t v0 = ws.cmp_chunk_dst[c0];
+            bool all_full = (v0 & CMP_DST_FULL) != 0;
+            for (int c = 1; c < rc && u * rc + c < nch; ++c) all_full = all_full && (ws.cmp_chunk_dst[c0 + c] & CMP_DST_FULL) != 0;
+            ws.run_dst[runs_before + u] = (v0 & ~CMP_DST_FULL) | (all_full ? CMP_DST_FULL : 0);
+        }
+    }
     if (tid == 0) {
         if (running != kept[g]) atomicOr(ws.err, ERR_MISMATCH);
         if (!inplace) {                                           // (in place the other blocks are still reading the lengths:

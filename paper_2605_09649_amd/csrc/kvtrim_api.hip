@@ -82,6 +82,7 @@ static Layout layout_of(const kvtrim_config* c) {
     l.off[20] = bump(cur, (size_t)nseg * sizeof(int32_t));                     // pg_seg_len
     l.off[21] = bump(cur, (size_t)c->n_seq * sizeof(uint32_t));                // seq_done
     l.off[22] = bump(cur, (size_t)nseg * sizeof(int32_t));                     // chunk_old_len
+    l.off[23] = bump(cur, l.max_att_chunks * sizeof(int64_t));                 // run_dst
     l.total = (cur + 255) & ~(size_t)255;
     return l;
 }
@@ -195,6 +196,7 @@ kvtrim_status kvtrim_create(kvtrim_ctx** out, const kvtrim_config* cfg) {
     w.pg_seg_len = (int32_t*)(b + l.off[20]);
     w.seq_done = (uint32_t*)(b + l.off[21]);
     w.chunk_old_len = (int32_t*)(b + l.off[22]);
+    w.run_dst = (int64_t*)(b + l.off[23]);
     w.max_sel_chunks = l.max_sel_chunks;
     w.max_cmp_chunks = l.max_cmp_chunks;
     w.max_att_chunks = l.max_att_chunks;

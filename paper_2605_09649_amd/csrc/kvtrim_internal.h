@@ -104,6 +104,7 @@ struct Workspace {
     int32_t* cmp_chunk_prefix;   // [nseg+1]
     ChunkDesc* cmp_desc;         // [max_cmp_chunks]
     int64_t* cmp_chunk_dst;      // [max_cmp_chunks] first dst entry of the chunk's survivors (| CMP_DST_FULL)
+    int64_t* run_dst;            // [max_att_chunks] the same per run of the loop-shaped fused kernel (flag: every chunk of the run is full)
     // attention
     int32_t* att_chunk_prefix;   // [nseg+1]
     ChunkDesc* att_desc;         // [max_att_chunks]
