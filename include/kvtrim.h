@@ -213,6 +213,12 @@ kvtrim_status kvtrim_compact_attn_inplace(kvtrim_ctx *ctx, kvtrim_cache *c, cons
 kvtrim_status kvtrim_compact_inplace(kvtrim_ctx *ctx, kvtrim_cache *c, const uint8_t *keep, const int32_t *kept,
                                      kvtrim_cache *spare, void *hip_stream);
 
+/* For callers of the in-place calls: min_room_out[0] (device int32) = the smallest number of free
+ * slots behind any segment (up to the next segment's start, or cap_entries for the last one) - how
+ * many more tokens per segment kvtrim_append can take for certain before an out-of-place step has
+ * to even the room out.  One small kernel; read the result back whenever convenient. */
+kvtrim_status kvtrim_min_room(kvtrim_ctx *ctx, const kvtrim_cache *c, int32_t *min_room_out, void *hip_stream);
+
 /* Support - new tokens enter the cache (Sec. 3.2: beta is fixed when the token is
  * first cached).  Appends up to n_new entries to every segment, in order, behind its
  * current end and adds their number to seg_len.  k_new, v_new: device bf16

@@ -8,7 +8,7 @@ the first call does, and fails loudly if it has not been built.
 from .binding import (PAGE_SIZE, Cache, Context, Gate, KvtrimError, PagedCache, kvtrim_gate_forward,
                       kvtrim_gate_forward_prepared, kvtrim_gate_prepare, kvtrim_gate_prepared_bytes,
                       kvtrim_gate_scratch_bytes, kvtrim_append, kvtrim_append_compact, kvtrim_compact,
-                      kvtrim_compact_attn, kvtrim_compact_attn_inplace, kvtrim_compact_inplace, kvtrim_decode_attn, kvtrim_decode_attn_soft, kvtrim_kernel_name,
+                      kvtrim_compact_attn, kvtrim_compact_attn_inplace, kvtrim_compact_inplace, kvtrim_decode_attn, kvtrim_decode_attn_soft, kvtrim_kernel_name, kvtrim_min_room,
                       kvtrim_occupancy, kvtrim_paged_append, kvtrim_paged_attn, kvtrim_paged_build,
                       kvtrim_paged_defrag, kvtrim_paged_evict, kvtrim_paged_score, kvtrim_paged_select, kvtrim_poll_error,
                       kvtrim_profile_begin, kvtrim_profile_end, kvtrim_score, kvtrim_select_global,
@@ -17,7 +17,7 @@ from .binding import (PAGE_SIZE, Cache, Context, Gate, KvtrimError, PagedCache, 
 __all__ = ["PAGE_SIZE", "Cache", "Context", "Gate", "KvtrimError", "PagedCache", "kvtrim_gate_forward",
            "kvtrim_gate_forward_prepared", "kvtrim_gate_prepare", "kvtrim_gate_prepared_bytes",
            "kvtrim_gate_scratch_bytes", "kvtrim_append", "kvtrim_append_compact", "kvtrim_compact",
-           "kvtrim_compact_attn", "kvtrim_compact_attn_inplace", "kvtrim_compact_inplace", "kvtrim_decode_attn", "kvtrim_decode_attn_soft", "kvtrim_kernel_name",
+           "kvtrim_compact_attn", "kvtrim_compact_attn_inplace", "kvtrim_compact_inplace", "kvtrim_decode_attn", "kvtrim_decode_attn_soft", "kvtrim_kernel_name", "kvtrim_min_room",
            "kvtrim_occupancy", "kvtrim_paged_append", "kvtrim_paged_attn", "kvtrim_paged_build",
            "kvtrim_paged_defrag", "kvtrim_paged_evict", "kvtrim_paged_score", "kvtrim_paged_select", "kvtrim_poll_error",
            "kvtrim_profile_begin", "kvtrim_profile_end", "kvtrim_score", "kvtrim_select_global",

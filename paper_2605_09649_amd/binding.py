@@ -13,7 +13,7 @@ STATUS = {0: "KVTRIM_OK", -1: "KVTRIM_EINVAL", -2: "KVTRIM_ENOMEM", -3: "KVTRIM_
 
 EXPORTS = ["kvtrim_create", "kvtrim_destroy", "kvtrim_workspace_bytes", "kvtrim_last_error",
            "kvtrim_poll_error", "kvtrim_score", "kvtrim_select_global", "kvtrim_compact",
-           "kvtrim_decode_attn", "kvtrim_decode_attn_soft", "kvtrim_occupancy", "kvtrim_compact_attn", "kvtrim_compact_inplace", "kvtrim_compact_attn_inplace", "kvtrim_append", "kvtrim_append_compact",
+           "kvtrim_decode_attn", "kvtrim_decode_attn_soft", "kvtrim_occupancy", "kvtrim_compact_attn", "kvtrim_min_room", "kvtrim_compact_inplace", "kvtrim_compact_attn_inplace", "kvtrim_append", "kvtrim_append_compact",
            "kvtrim_paged_build", "kvtrim_paged_append", "kvtrim_paged_score", "kvtrim_paged_select",
            "kvtrim_paged_evict", "kvtrim_paged_defrag", "kvtrim_paged_attn", "kvtrim_gate_scratch_bytes", "kvtrim_gate_forward", "kvtrim_gate_prepared_bytes", "kvtrim_gate_prepare",
            "kvtrim_gate_forward_prepared",
@@ -84,6 +84,7 @@ def load_library():
         lib.kvtrim_compact_attn.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.POINTER(_Cache),
                                             C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p,
                                             C.c_void_p, C.c_void_p]
+        lib.kvtrim_min_room.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_void_p]
         lib.kvtrim_compact_inplace.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.POINTER(_Cache), C.c_void_p]
         lib.kvtrim_compact_attn_inplace.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.POINTER(_Cache),
                                                     C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p,
@@ -309,6 +310,11 @@ def kvtrim_compact_attn(ctx, src, keep, kept, dst, reserve, q, layer_begin, laye
         ctx.handle, C.byref(src.c), _ptr(keep, torch.uint8), _ptr(kept, torch.int32), C.byref(dst.c), int(reserve),
         _ptr(q, torch.bfloat16), int(layer_begin), int(layer_end), float(softmax_scale), _ptr(out, torch.float32),
         _ptr(lse, torch.float32), _stream(stream)), "kvtrim_compact_attn")
+
+
+def kvtrim_min_room(ctx, cache, min_room_out, stream=None):
+    _check(ctx, load_library().kvtrim_min_room(ctx.handle, C.byref(cache.c), _ptr(min_room_out, torch.int32), _stream(stream)),
+           "kvtrim_min_room")
 
 
 def kvtrim_compact_inplace(ctx, cache, keep, kept, spare, stream=None):

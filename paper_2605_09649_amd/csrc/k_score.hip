@@ -127,6 +127,28 @@ __global__ __launch_bounds__(256) void k_append(CacheViewMut c, const uint16_t* 
     if (threadIdx.x == 0) c.seg_len[seg] = len + cnt;
 }
 
+// min over the segments of the free slots behind them (up to the next segment's start, or the end of the buffers)
+__global__ __launch_bounds__(1024) void k_min_room(CacheView c, int nseg, int32_t* __restrict__ out) {
+    __shared__ int s_min;
+    if (threadIdx.x == 0) s_min = 0x7fffffff;
+    __syncthreads();
+    int64_t mine = 0x7fffffff;
+    for (int g = threadIdx.x; g < nseg; g += blockDim.x) {
+        const int64_t end = c.seg_start[g] + c.seg_len[g];
+        const int64_t limit = g + 1 < nseg ? c.seg_start[g + 1] : c.cap;
+        mine = min(mine, limit - end);
+    }
+    atomicMin(&s_min, (int)max(min(mine, (int64_t)0x7fffffff), (int64_t)-0x7fffffff));
+    __syncthreads();
+    if (threadIdx.x == 0) out[0] = s_min;
+}
+
+kvtrim_status launch_min_room(kvtrim_ctx* ctx, const CacheView& c, int32_t* out, hipStream_t st) {
+    hipLaunchKernelGGL(k_min_room, dim3(1), dim3(1024), 0, st, c, ctx->shape.nseg, out);
+    KVTRIM_HIP(ctx, hipGetLastError());
+    return KVTRIM_OK;
+}
+
 kvtrim_status launch_append(kvtrim_ctx* ctx, const CacheViewMut& c, const uint16_t* k_new, const uint16_t* v_new,
                             const float* lb_new, const float* lt_new, const int32_t* pos_new, int32_t n_new,
                             bool copy_rows, int32_t* old_len_out, hipStream_t st) {

@@ -399,6 +399,13 @@ static const char* inplace_problem(const kvtrim_ctx* ctx, const kvtrim_cache* c,
     return nullptr;
 }
 
+kvtrim_status kvtrim_min_room(kvtrim_ctx* ctx, const kvtrim_cache* c, int32_t* min_room_out, void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    if (const char* p = cache_problem(ctx, c, false)) return invalid(ctx, p);
+    if (!min_room_out) return invalid(ctx, "min_room_out is NULL");
+    return launch_min_room(ctx, view_of(c), min_room_out, (hipStream_t)hip_stream);
+}
+
 kvtrim_status kvtrim_compact_inplace(kvtrim_ctx* ctx, kvtrim_cache* c, const uint8_t* keep, const int32_t* kept,
                                      kvtrim_cache* spare, void* hip_stream) {
     if (!ctx) return KVTRIM_EINVAL;

@@ -198,6 +198,8 @@ kvtrim_status launch_cmp_copy_new(kvtrim_ctx*, const CacheView& src, const uint8
                                   const uint16_t* k_new, const uint16_t* v_new, int32_t n_new, const int32_t* old_len,
                                   hipStream_t);
 
+kvtrim_status launch_min_room(kvtrim_ctx*, const CacheView&, int32_t* out, hipStream_t);
+
 kvtrim_status hip_fail(kvtrim_ctx* ctx, hipError_t e, const char* what);
 
 #define KVTRIM_HIP(ctx, expr)                                          \

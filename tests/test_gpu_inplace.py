@@ -148,3 +148,30 @@ def test_in_place_layer_range(G):
     assert bool((outs[1][:, 0] == 7.0).all()) and bool((outs[1][:, 2] == 7.0).all())
     from harness import compare_cache_contents, device_cache_to_host
     assert compare_cache_contents(device_cache_to_host(w, b), device_cache_to_host(w, a))
+
+
+def test_min_room_follows_the_segments():
+    # free slots behind the tightest segment: after an out-of-place step with a reserve, after appends, after an
+    # in-place step that evicts from every segment
+    w = wl(1, 2, 2, 2, 64)
+    seg_len = [300, 10, 129, 77]
+    c, now = ki.ragged_cache(w, seg_len, reserve=5, salt=4)
+    cap = c["cap"]
+    ctx = kv.Context(1, 2, 2, 4, 64, cap)
+    cache, spare = kv.Cache.from_dict(c, DEV), kv.Cache.empty(w.nseg, 64, cap, DEV)
+    room = torch.zeros(1, dtype=torch.int32, device=DEV)
+    kv.kvtrim_min_room(ctx, cache, room)
+    assert int(room.item()) == 5
+    inp = {k: v.to(DEV) for k, v in ki.decode_inputs(w, 0).items()}
+    pos = torch.full((w.nseg,), int(now[0]) + 1, dtype=torch.int32, device=DEV)
+    kv.kvtrim_append(ctx, cache, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos, 1)
+    kv.kvtrim_min_room(ctx, cache, room)
+    assert int(room.item()) == 4
+    score, keep = torch.zeros(cap, dtype=torch.float32, device=DEV), torch.zeros(cap, dtype=torch.uint8, device=DEV)
+    kept = torch.zeros(w.nseg, dtype=torch.int32, device=DEV)
+    kv.kvtrim_score(ctx, cache, (now + 1).to(DEV), score)
+    kv.kvtrim_select_global(ctx, cache, score, torch.tensor([0], dtype=torch.int64, device=DEV), keep, kept)
+    kv.kvtrim_compact_inplace(ctx, cache, keep, kept, spare)          # budget 0: every segment is emptied where it stands
+    kv.kvtrim_min_room(ctx, cache, room)
+    assert kv.kvtrim_poll_error(ctx) == 0
+    assert int(room.item()) == min(seg_len) + 5 and int(cache.seg_len.sum().item()) == 0
