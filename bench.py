@@ -24,7 +24,8 @@ CPU_STEPS = 16                 # steps the CPU oracle replays after the timed re
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs, scaled by a plain copy kernel; None until measured for this workload.
 MEASURED_TRAFFIC = {("long", "k_cmp_attn"): 1.1011e9 + 1.1259e9, ("long", "k_cmp_copy"): None,
-                    ("long-paged", "k_att_partial"): 1.0942e9 + 8.8e6, ("gate-1", "k_gate_hidden"): 136.5e6 + 65.5e3}
+                    ("long-paged", "k_att_partial"): 1.0942e9 + 8.8e6, ("gate-1", "k_gate_hidden"): 136.5e6 + 65.5e3,
+                    ("long-inplace", "k_cmp_attn"): 1.1012e9 + 0.2459e9}
 
 
 def rows_moved_in_place(cache, keep):
@@ -612,7 +613,7 @@ def main():
                        "bytes_by_stage": alg},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None if args.inplace else MEASURED_TRAFFIC.get((w.name + ("-paged" if args.paged else ""), dom)),
+                     "traffic": MEASURED_TRAFFIC.get((w.name + ("-paged" if args.paged else "-inplace" if args.inplace else ""), dom)),
                      "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_avg_ms, "launches": dom_n,
                      "stage_model_bytes_per_launch": stage_model_bytes,
                      "stage_model_achieved": (stage_model_bytes / (dom_avg_ms * 1e-3) / 1e9) if stage_model_bytes else None,
