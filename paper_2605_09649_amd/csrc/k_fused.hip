@@ -118,7 +118,8 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
     int cnt = 0;
     float md_lb = 0.f, md_lt = 0.f;
     int md_pos = 0, md_rank = tid;
-    bool md_mine = full && tid < cd.n;                            // this thread carries an entry's metadata in registers
+    // this thread carries an entry's metadata in registers (INPLACE: not if the chunk stays as it is)
+    bool md_mine = full && tid < cd.n && !(INPLACE && dbase == sbase);
     if (full) {
         cnt = cd.n;
         if (md_mine) {
