@@ -406,6 +406,26 @@ kvtrim_status kvtrim_gate_forward_prepared(kvtrim_ctx *ctx, const kvtrim_gate *g
                                            int32_t n_tok, int32_t layer_begin, int32_t layer_end, int32_t horizon,
                                            void *scratch, float *log_beta_out, float *log_tail_out, void *hip_stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): kvtrim_select_global without a context.  Same selection rule, same kernels, same
+ * outputs (keep_out, kept_out, thr_key_out) as kvtrim_select_global; the tables that call keeps in its context's
+ * workspace live in one fixed array of KVTRIM_NOALLOC_SCRATCH_BYTES bytes inside the library instead (each GPU
+ * the library runs on holds its own copy until the process ends).  The call makes no hipMalloc / hipFree and calls
+ * no allocating routine; it only enqueues kernels on `hip_stream`.
+ *   cfg         host pointer: the shape (n_seq, n_layers, n_kv_heads, ...) and max_entries >= c->cap_entries.
+ *               The tables grow with n_seq (about 200 KB each) and with max_entries (28 bytes per 2048 entries)
+ *               plus 12 bytes per segment; a configuration whose tables exceed the array - e.g. more than about
+ *               40 sequences - is rejected with KVTRIM_EINVAL before anything is launched.
+ *   c, score, budget, keep_out, kept_out, thr_key_out: as in kvtrim_select_global (caller-owned device memory).
+ *   status_out  optional device int32 [1]: written by the call's last kernel with KVTRIM_OK, or KVTRIM_ELAYOUT
+ *               when the segment table does not fit cap_entries (then keep_out / kept_out are unspecified).
+ * All calls on one GPU share that GPU's array: they must be ordered (one stream, or events between streams);
+ * calls that overlap on one GPU race.  Nothing carries over from one call to the next. */
+#define KVTRIM_NOALLOC_SCRATCH_BYTES 8388608
+kvtrim_status kvtrim_select_global_noalloc(const kvtrim_config *cfg, const kvtrim_cache *c, const float *score,
+                                           const int64_t *budget, uint8_t *keep_out, int32_t *kept_out,
+                                           uint32_t *thr_key_out, int32_t *status_out, void *hip_stream);
+
 /* Instrumentation (for the benchmark; not a step of the method).  Between
  * kvtrim_profile_begin and kvtrim_profile_end every launch of a kernel whose bit is
  * set in `kernel_mask` (bit i = kernel id i, names from kvtrim_kernel_name) is

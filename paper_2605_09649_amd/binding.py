@@ -17,6 +17,7 @@ EXPORTS = ["kvtrim_create", "kvtrim_destroy", "kvtrim_workspace_bytes", "kvtrim_
            "kvtrim_paged_build", "kvtrim_paged_append", "kvtrim_paged_score", "kvtrim_paged_select",
            "kvtrim_paged_evict", "kvtrim_paged_defrag", "kvtrim_paged_attn", "kvtrim_gate_scratch_bytes", "kvtrim_gate_forward", "kvtrim_gate_prepared_bytes", "kvtrim_gate_prepare",
            "kvtrim_gate_forward_prepared",
+           "kvtrim_select_global_noalloc",
            "kvtrim_profile_begin", "kvtrim_profile_end",
            "kvtrim_kernel_name"]
 PAGE_SIZE = 128
@@ -114,6 +115,8 @@ def load_library():
         lib.kvtrim_gate_prepare.argtypes = [C.c_void_p, C.POINTER(_Gate), C.c_void_p, C.c_void_p]
         lib.kvtrim_gate_forward_prepared.argtypes = [C.c_void_p, C.POINTER(_Gate), C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                                      C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.kvtrim_select_global_noalloc.argtypes = [C.POINTER(_Config), C.POINTER(_Cache), C.c_void_p, C.c_void_p,
+                                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.kvtrim_profile_begin.argtypes = [C.c_void_p, C.c_uint32]
         lib.kvtrim_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         lib.kvtrim_kernel_name.argtypes = [C.c_int32]
@@ -277,6 +280,18 @@ def kvtrim_select_global(ctx, cache, score, budget, keep_out, kept_out, thr_key_
         ctx.handle, C.byref(cache.c), _ptr(score, torch.float32), _ptr(budget, torch.int64),
         _ptr(keep_out, torch.uint8), _ptr(kept_out, torch.int32), _ptr(thr_key_out), _stream(stream)),
         "kvtrim_select_global")
+
+
+def kvtrim_select_global_noalloc(config, cache, score, budget, keep_out, kept_out, thr_key_out=None, status_out=None,
+                                 stream=None):
+    """config: (n_seq, n_layers, n_kv_heads, n_q_heads, head_dim, max_entries); no context is involved."""
+    cfg = _config(*config)
+    rc = load_library().kvtrim_select_global_noalloc(
+        C.byref(cfg), C.byref(cache.c), _ptr(score, torch.float32), _ptr(budget, torch.int64),
+        _ptr(keep_out, torch.uint8), _ptr(kept_out, torch.int32), _ptr(thr_key_out), _ptr(status_out, torch.int32),
+        _stream(stream))
+    if rc != 0:
+        raise KvtrimError(rc, "kvtrim_select_global_noalloc")
 
 
 def kvtrim_compact(ctx, src, keep, kept, dst, reserve, stream=None):

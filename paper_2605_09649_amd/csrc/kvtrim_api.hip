@@ -44,20 +44,22 @@ static size_t bump(size_t& cur, size_t bytes) {
     return at;
 }
 
-static Layout layout_of(const kvtrim_config* c) {
+// select_only: the arrays of the compaction and the attention get no room (a workspace for stage 2 alone).
+static Layout layout_of(const kvtrim_config* c, bool select_only) {
     Layout l;
     const int64_t nseg = (int64_t)c->n_seq * c->n_layers * c->n_kv_heads;
     const int G = c->n_q_heads / c->n_kv_heads;
     l.max_sel_chunks = c->max_entries / SEL_CHUNK + nseg;
-    l.max_cmp_chunks = c->max_entries / CMP_CHUNK + nseg;
+    l.max_cmp_chunks = select_only ? 0 : c->max_entries / CMP_CHUNK + nseg;
     // the attention chunk grows with the capacity (att_chunk_for) so that at most 16384 full
     // chunks plus one ragged tail per segment ever exist
     // (the fused stage 3+4 kernel also writes one partial result per 128-entry compaction chunk;
     // it is used for caches of up to 524288 such chunks = 67 M entries, larger ones take the two-call path;
     // the buffer is [chunk][G][D + 2] fp32, 2 KB per chunk at G = 4, D = 128)
     const int64_t full = c->max_entries / CMP_CHUNK < 524288 ? c->max_entries / CMP_CHUNK : 524288;
-    const int64_t att = full + nseg + 1;
+    const int64_t att = select_only ? 0 : full + nseg + 1;
     l.max_att_chunks = att;
+    const size_t seg_tables = select_only ? 0 : 1;                             // per-segment arrays the selection does not use
     size_t cur = 0;
     l.off[0] = bump(cur, (nseg + 1) * sizeof(int32_t));                        // sel_chunk_prefix
     l.off[1] = bump(cur, l.max_sel_chunks * sizeof(ChunkDesc));                // sel_desc
@@ -66,25 +68,75 @@ static Layout layout_of(const kvtrim_config* c) {
     l.off[4] = bump(cur, DONE_WORDS * sizeof(uint32_t));                       // done
     l.off[5] = bump(cur, l.max_sel_chunks * sizeof(int32_t));                  // chunk_eq
     l.off[6] = bump(cur, l.max_sel_chunks * sizeof(int64_t));                  // chunk_tie_base
-    l.off[7] = bump(cur, (nseg + 1) * sizeof(int32_t));                        // cmp_chunk_prefix
+    l.off[7] = bump(cur, seg_tables * (nseg + 1) * sizeof(int32_t));           // cmp_chunk_prefix
     l.off[8] = bump(cur, l.max_cmp_chunks * sizeof(ChunkDesc));                // cmp_desc
     l.off[9] = bump(cur, l.max_cmp_chunks * sizeof(int64_t));                  // cmp_chunk_dst
-    l.off[10] = bump(cur, (nseg + 1) * sizeof(int32_t));                       // att_chunk_prefix
+    l.off[10] = bump(cur, seg_tables * (nseg + 1) * sizeof(int32_t));          // att_chunk_prefix
     l.off[11] = bump(cur, l.max_att_chunks * sizeof(ChunkDesc));               // att_desc
     l.off[12] = bump(cur, (size_t)l.max_att_chunks * G * (c->head_dim + 2) * sizeof(float)); // att_partial
     l.off[13] = bump(cur, 256);                                                // err
     l.off[14] = bump(cur, (nseg + 1) * sizeof(int64_t));                       // sel_entry_prefix
     l.off[15] = bump(cur, HIST_BLOCKS_MAX * sizeof(int4));                     // sel_blk
-    l.off[16] = bump(cur, (size_t)nseg * sizeof(int32_t));                     // tie_cnt
-    l.off[17] = bump(cur, (size_t)nseg * sizeof(int32_t));                     // tie_mode
-    l.off[18] = bump(cur, (size_t)nseg * sizeof(int32_t));                     // tie_thr
-    l.off[19] = bump(cur, (size_t)nseg * sizeof(int64_t));                     // pg_seg_start
-    l.off[20] = bump(cur, (size_t)nseg * sizeof(int32_t));                     // pg_seg_len
+    l.off[16] = bump(cur, seg_tables * (size_t)nseg * sizeof(int32_t));        // tie_cnt
+    l.off[17] = bump(cur, seg_tables * (size_t)nseg * sizeof(int32_t));        // tie_mode
+    l.off[18] = bump(cur, seg_tables * (size_t)nseg * sizeof(int32_t));        // tie_thr
+    l.off[19] = bump(cur, seg_tables * (size_t)nseg * sizeof(int64_t));        // pg_seg_start
+    l.off[20] = bump(cur, seg_tables * (size_t)nseg * sizeof(int32_t));        // pg_seg_len
     l.off[21] = bump(cur, (size_t)c->n_seq * sizeof(uint32_t));                // seq_done
-    l.off[22] = bump(cur, (size_t)nseg * sizeof(int32_t));                     // chunk_old_len
+    l.off[22] = bump(cur, seg_tables * (size_t)nseg * sizeof(int32_t));        // chunk_old_len
     l.off[23] = bump(cur, l.max_att_chunks * sizeof(int64_t));                 // run_dst
     l.total = (cur + 255) & ~(size_t)255;
     return l;
+}
+
+static void bind(const Layout& l, char* b, Workspace& w) {
+    w.sel_chunk_prefix = (int32_t*)(b + l.off[0]);
+    w.sel_desc = (ChunkDesc*)(b + l.off[1]);
+    w.hist = (uint32_t*)(b + l.off[2]);
+    w.sel = (SelState*)(b + l.off[3]);
+    w.done = (uint32_t*)(b + l.off[4]);
+    w.chunk_eq = (int32_t*)(b + l.off[5]);
+    w.chunk_tie_base = (int64_t*)(b + l.off[6]);
+    w.cmp_chunk_prefix = (int32_t*)(b + l.off[7]);
+    w.cmp_desc = (ChunkDesc*)(b + l.off[8]);
+    w.cmp_chunk_dst = (int64_t*)(b + l.off[9]);
+    w.att_chunk_prefix = (int32_t*)(b + l.off[10]);
+    w.att_desc = (ChunkDesc*)(b + l.off[11]);
+    w.att_partial = (float*)(b + l.off[12]);
+    w.pg_block_table = nullptr;
+    w.err = (int32_t*)(b + l.off[13]);
+    w.sel_entry_prefix = (int64_t*)(b + l.off[14]);
+    w.sel_blk = (int4*)(b + l.off[15]);
+    w.tie_cnt = (int32_t*)(b + l.off[16]);
+    w.tie_mode = (int32_t*)(b + l.off[17]);
+    w.tie_thr = (int32_t*)(b + l.off[18]);
+    w.pg_seg_start = (int64_t*)(b + l.off[19]);
+    w.pg_seg_len = (int32_t*)(b + l.off[20]);
+    w.seq_done = (uint32_t*)(b + l.off[21]);
+    w.chunk_old_len = (int32_t*)(b + l.off[22]);
+    w.run_dst = (int64_t*)(b + l.off[23]);
+    w.max_sel_chunks = l.max_sel_chunks;
+    w.max_cmp_chunks = l.max_cmp_chunks;
+    w.max_att_chunks = l.max_att_chunks;
+}
+
+bool config_valid(const kvtrim_config* c) { return config_ok(c); }
+
+void shape_of(const kvtrim_config* cfg, Shape& sh) {
+    sh.n_seq = cfg->n_seq;
+    sh.n_layers = cfg->n_layers;
+    sh.n_kv_heads = cfg->n_kv_heads;
+    sh.n_q_heads = cfg->n_q_heads;
+    sh.head_dim = cfg->head_dim;
+    sh.segs_per_seq = cfg->n_layers * cfg->n_kv_heads;
+    sh.nseg = cfg->n_seq * sh.segs_per_seq;
+    sh.group = cfg->n_q_heads / cfg->n_kv_heads;
+}
+
+size_t select_workspace(const kvtrim_config* cfg, char* base, Workspace* ws) {
+    const Layout l = layout_of(cfg, true);
+    if (ws) bind(l, base, *ws);
+    return l.total;
 }
 
 static CacheView view_of(const kvtrim_cache* c) {
@@ -130,7 +182,7 @@ extern "C" {
 
 size_t kvtrim_workspace_bytes(const kvtrim_config* cfg) {
     if (!config_ok(cfg)) return 0;
-    return layout_of(cfg).total;
+    return layout_of(cfg, false).total;
 }
 
 kvtrim_status kvtrim_create(kvtrim_ctx** out, const kvtrim_config* cfg) {
@@ -141,21 +193,13 @@ kvtrim_status kvtrim_create(kvtrim_ctx** out, const kvtrim_config* cfg) {
     if (!ctx) return KVTRIM_ENOMEM;
     memset(ctx, 0, sizeof(*ctx));
     ctx->cfg = *cfg;
-    Shape& sh = ctx->shape;
-    sh.n_seq = cfg->n_seq;
-    sh.n_layers = cfg->n_layers;
-    sh.n_kv_heads = cfg->n_kv_heads;
-    sh.n_q_heads = cfg->n_q_heads;
-    sh.head_dim = cfg->head_dim;
-    sh.segs_per_seq = cfg->n_layers * cfg->n_kv_heads;
-    sh.nseg = cfg->n_seq * sh.segs_per_seq;
-    sh.group = cfg->n_q_heads / cfg->n_kv_heads;
+    shape_of(cfg, ctx->shape);
     ctx->att_chunk_min = 512;
     if (const char* e = getenv("KVTRIM_ATT_CHUNK")) {            // tuning knob: rows per attention chunk
         const int v = atoi(e);
         if (v >= 256 && v <= 65536 && v % 64 == 0) ctx->att_chunk_min = v;
     }
-    const Layout l = layout_of(cfg);
+    const Layout l = layout_of(cfg, false);
     ctx->ws_bytes = l.total;
     if (hipGetDevice(&ctx->device) != hipSuccess || hipMalloc(&ctx->ws_base, l.total) != hipSuccess) {
         (void)hipGetLastError();
@@ -170,36 +214,7 @@ kvtrim_status kvtrim_create(kvtrim_ctx** out, const kvtrim_config* cfg) {
         delete ctx;
         return KVTRIM_EHIP;
     }
-    char* b = (char*)ctx->ws_base;
-    Workspace& w = ctx->ws;
-    w.sel_chunk_prefix = (int32_t*)(b + l.off[0]);
-    w.sel_desc = (ChunkDesc*)(b + l.off[1]);
-    w.hist = (uint32_t*)(b + l.off[2]);
-    w.sel = (SelState*)(b + l.off[3]);
-    w.done = (uint32_t*)(b + l.off[4]);
-    w.chunk_eq = (int32_t*)(b + l.off[5]);
-    w.chunk_tie_base = (int64_t*)(b + l.off[6]);
-    w.cmp_chunk_prefix = (int32_t*)(b + l.off[7]);
-    w.cmp_desc = (ChunkDesc*)(b + l.off[8]);
-    w.cmp_chunk_dst = (int64_t*)(b + l.off[9]);
-    w.att_chunk_prefix = (int32_t*)(b + l.off[10]);
-    w.att_desc = (ChunkDesc*)(b + l.off[11]);
-    w.att_partial = (float*)(b + l.off[12]);
-    w.pg_block_table = nullptr;
-    w.err = (int32_t*)(b + l.off[13]);
-    w.sel_entry_prefix = (int64_t*)(b + l.off[14]);
-    w.sel_blk = (int4*)(b + l.off[15]);
-    w.tie_cnt = (int32_t*)(b + l.off[16]);
-    w.tie_mode = (int32_t*)(b + l.off[17]);
-    w.tie_thr = (int32_t*)(b + l.off[18]);
-    w.pg_seg_start = (int64_t*)(b + l.off[19]);
-    w.pg_seg_len = (int32_t*)(b + l.off[20]);
-    w.seq_done = (uint32_t*)(b + l.off[21]);
-    w.chunk_old_len = (int32_t*)(b + l.off[22]);
-    w.run_dst = (int64_t*)(b + l.off[23]);
-    w.max_sel_chunks = l.max_sel_chunks;
-    w.max_cmp_chunks = l.max_cmp_chunks;
-    w.max_att_chunks = l.max_att_chunks;
+    bind(l, (char*)ctx->ws_base, ctx->ws);
     *out = ctx;
     return KVTRIM_OK;
 }

@@ -202,6 +202,13 @@ kvtrim_status launch_min_room(kvtrim_ctx*, const CacheView&, int32_t* out, hipSt
 
 kvtrim_status hip_fail(kvtrim_ctx* ctx, hipError_t e, const char* what);
 
+// Pieces of the context set-up that the entry point without a context shares: the config check, the shape
+// derived from a config, and the layout of a workspace that holds the tables of stage 2 only (returns its size
+// in bytes; binds `ws` to `base` when ws is not NULL).
+bool config_valid(const kvtrim_config* cfg);
+void shape_of(const kvtrim_config* cfg, Shape& sh);
+size_t select_workspace(const kvtrim_config* cfg, char* base, Workspace* ws);
+
 #define KVTRIM_HIP(ctx, expr)                                          \
     do {                                                               \
         hipError_t _e = (expr);                                        \
