@@ -309,6 +309,59 @@ def test_append_takes_rows_up_to_the_first_padding_row():
     assert not hc.k[34:48].any() and not hc.k[48:].any()          # nothing written behind the taken rows
 
 
+def test_compact_carries_the_horizon_tail_with_its_entry():
+    # a cache with the per-entry constant of a lookahead horizon H > 1 (Eq. global_score: log of the tail sum,
+    # fixed like beta when the token is cached): compaction moves it with its entry, bit for bit, and only then
+    rng = np.random.default_rng(21)
+    seg_len = rng.integers(0, 70, 8)
+    w, hc, _ = make(seg_len, L=2, H=4, reserve=2, salt=9)
+    tail = (-rng.random(hc.cap) * 3).astype(np.float32)           # distinct values, unrelated to log_beta
+    hc = oracle.HostCache.from_arrays(hc.shape, hc.k, hc.v, hc.log_beta, hc.pos, hc.seg_start, hc.seg_len, log_tail=tail.copy())
+    keep = (rng.random(hc.cap) < 0.5).astype(np.uint8)
+    dst = oracle.compact(hc, keep, int(keep.sum()) + 3 * w.nseg + 5, 3)
+    assert dst.log_tail is not None
+    for g in range(w.nseg):
+        s0, n = int(hc.seg_start[g]), int(hc.seg_len[g])
+        m = keep[s0:s0 + n].astype(bool)
+        d0 = int(dst.seg_start[g])
+        assert dst.seg_len[g] == m.sum()
+        np.testing.assert_array_equal(dst.log_tail[d0:d0 + m.sum()].view(np.uint32), tail[s0:s0 + n][m].view(np.uint32))
+        np.testing.assert_array_equal(dst.log_beta[d0:d0 + m.sum()].view(np.uint32),
+                                      hc.log_beta[s0:s0 + n][m].view(np.uint32))
+        np.testing.assert_array_equal(dst.pos[d0:d0 + m.sum()], hc.pos[s0:s0 + n][m])
+    # the tail changes the ranking, so a mix-up with log_beta or a shifted index would show: the two arrays differ
+    assert not np.array_equal(dst.log_tail[live_mask(dst)], dst.log_beta[live_mask(dst)])
+    # without a tail in the source there is none in the destination
+    w2, hc2, _ = make([4, 4, 4, 4])
+    assert oracle.compact(hc2, np.ones(hc2.cap, np.uint8), hc2.cap, 1).log_tail is None
+
+
+def test_append_writes_the_horizon_tail_of_the_new_tokens():
+    sh = oracle.Shape(2, 1, 2, 2, 4)
+    hc = oracle.HostCache(sh, 64, with_tail=True)
+    hc.seg_start[:] = [0, 16, 32, 48]
+    hc.log_tail[:] = 7.0                                           # sentinel: slots that no token takes keep it
+    rng = np.random.default_rng(5)
+    k = rng.integers(0, 60000, (4, 3, 4)).astype(np.uint16)
+    lb = -rng.random((4, 3)).astype(np.float32)
+    lt = rng.random((4, 3)).astype(np.float32)                     # log(1 + beta + ...) >= 0
+    pos = np.array([[0, 1, 2], [5, 6, -1], [-1, 0, 1], [3, 4, 9]], np.int32)
+    oracle.append(hc, k, k, lb, pos, log_tail_new=lt)
+    assert list(hc.seg_len) == [3, 2, 0, 3]
+    for g, n in enumerate(hc.seg_len):
+        s0 = hc.seg_start[g]
+        assert np.array_equal(hc.log_tail[s0:s0 + n].view(np.uint32), lt[g, :n].view(np.uint32))
+        assert np.array_equal(hc.log_beta[s0:s0 + n].view(np.uint32), lb[g, :n].view(np.uint32))
+        assert np.all(hc.log_tail[s0 + n:s0 + 16] == 7.0)          # padding rows and free slots untouched
+    # a second chunk lands behind the first, tails included
+    lt2 = rng.random((4, 3)).astype(np.float32)
+    oracle.append(hc, k, k, lb, np.where(pos >= 0, pos + 10, pos), log_tail_new=lt2)
+    assert list(hc.seg_len) == [6, 4, 0, 6]
+    assert np.array_equal(hc.log_tail[3:6], lt2[0]) and np.array_equal(hc.log_tail[18:20], lt2[1, :2])
+    with pytest.raises(AssertionError):                            # a cache with tails refuses tokens without one
+        oracle.append(hc, k, k, lb, pos)
+
+
 def test_the_attention_tolerance_is_not_limited_by_the_oracle():
     # the same attention evaluated in fp32 (torch CPU, bf16 inputs widened exactly) lands within 1e-5 of the fp64
     # oracle in the benchmark's error metric: the 5e-3 tolerance of the GPU parity tests has three orders of
