@@ -327,6 +327,8 @@ def main():
     ap.add_argument("--inplace", type=int, default=0, metavar="ROOM",
                     help="compact inside the cache (kvtrim_compact_attn_inplace: rows move only behind an eviction) with ROOM "
                          "free slots behind every segment; every ROOM-th step is an out-of-place step that evens the room out")
+    ap.add_argument("--separate-score-select", action="store_true",
+                    help="run stages 1 and 2 as two calls (kvtrim_score, kvtrim_select_global) instead of kvtrim_score_select")
     ap.add_argument("--one-call", action="store_true",
                     help="with --chunk (ragged layout): the chunk step through kvtrim_append_compact, which moves the new rows "
                          "once, from the caller's buffers to the compacted cache")
@@ -426,8 +428,11 @@ def main():
             return
         kv.kvtrim_append(ctx, cur, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos_news[s], 1,
                          log_tail_new=inp.get("log_tail_new"))
-        kv.kvtrim_score(ctx, cur, nows[s], score)
-        kv.kvtrim_select_global(ctx, cur, score, budget, keep, kept, thr)
+        if args.separate_score_select:
+            kv.kvtrim_score(ctx, cur, nows[s], score)
+            kv.kvtrim_select_global(ctx, cur, score, budget, keep, kept, thr)
+        else:                                   # first step: eviction from the whole prefill (hint 0: the radix passes)
+            kv.kvtrim_score_select(ctx, cur, nows[s], budget, score, keep, kept, thr, evict_hint=per_seq if s > 0 else 0)
         if args.paged:                          # first step: the survivors of the prefill go into pages
             kv.kvtrim_paged_build(ctx, cur, keep, kept, pc)
             kv.kvtrim_paged_attn(ctx, pc, inp["q"], 0, w.n_layers, scale, out, lse)
@@ -507,6 +512,8 @@ def main():
         for name, (ms, n) in sorted(prof.items(), key=lambda kvp: -kvp[1][0]):
             log(f"[bench]   {name:16s} {ms / n * 1e3:8.1f} us x {n}")
     ms_per_step = (t_end - t_begin) * 1e3 / K
+    sel_paths = kv.kvtrim_select_path_counts(ctx)
+    log(f"[bench] decode-step selections so far: {sel_paths[0]} from the candidate list, {sel_paths[1]} by the single-block fallback")
     inplace_info = None
     alg = algorithmic_bytes(w, n_cand, n_ret, args.horizon)
     alg_total = sum(alg.values())

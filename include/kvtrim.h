@@ -6,10 +6,10 @@
  *
  * One decode / eviction step is
  *     kvtrim_append  (support: the new token enters every segment)
- *  -> kvtrim_score          stage 1
- *  -> kvtrim_select_global  stage 2
- *  -> kvtrim_compact        stage 3
- *  -> kvtrim_decode_attn    stage 4
+ *  -> kvtrim_score          stage 1      } or both in one call:
+ *  -> kvtrim_select_global  stage 2      } kvtrim_score_select
+ *  -> kvtrim_compact        stage 3      } or both in one call:
+ *  -> kvtrim_decode_attn    stage 4      } kvtrim_compact_attn
  *
  * Common rules
  *  - Every call returns a kvtrim_status; nothing throws or aborts.  Host-visible
@@ -127,6 +127,33 @@ kvtrim_status kvtrim_score(kvtrim_ctx *ctx, const kvtrim_cache *c, const int32_t
 kvtrim_status kvtrim_select_global(kvtrim_ctx *ctx, const kvtrim_cache *c, const float *score,
                                    const int64_t *budget, uint8_t *keep_out, int32_t *kept_out,
                                    uint32_t *thr_key_out, void *hip_stream);
+
+/* Stages 1 + 2 in one call: leaves in score_out, keep_out, kept_out and thr_key_out exactly what
+ *     kvtrim_score(c, now) -> kvtrim_select_global(c, score_out, budget)
+ * leave there (Sec. 4.2: Eq. (global_score), then the global eviction rule; same total order, same bits), with
+ * fewer passes over the cache.  Arguments as in those two calls.
+ * evict_hint (host value, a performance hint only - every value gives the same results): about how many entries
+ * each sequence loses in this call, e.g. n_layers * n_kv_heads * (tokens appended since the last selection) for a
+ * decode step at the budget; 0 = unknown or many (the first eviction after a prefill, a prefill chunk).
+ *   hint 0, or one beyond an eighth of the context's candidate list (511 for up to 256 sequences): the radix
+ *     passes of kvtrim_select_global, the first of which computes the score as it goes.
+ *   otherwise: one pass scores every entry and lists those whose key lies below a bound the context carries from
+ *     its previous selection; while a sequence needs k evictions and at least k + 1 entries are listed, the lowest
+ *     k + 1 entries of the order are among them and are ranked directly; then the mask pass.  Two kernels.  The
+ *     bound follows the threshold from call to call by itself.  A sequence whose list comes up short (no previous
+ *     selection on this context, a jump in the budget or the workload) or overflows is selected by a slow single-
+ *     block fallback inside the same kernel - correct, but about as slow as a millisecond per 2 M entries, so pass
+ *     0 when the number of evictions is not small.
+ * Device-side error: KVTRIM_ELAYOUT for a segment table that does not fit cap_entries or overlaps. */
+kvtrim_status kvtrim_score_select(kvtrim_ctx *ctx, const kvtrim_cache *c, const int32_t *now, const int64_t *budget,
+                                  float *score_out, uint8_t *keep_out, int32_t *kept_out, uint32_t *thr_key_out,
+                                  int64_t evict_hint, void *hip_stream);
+
+/* Diagnostics of kvtrim_score_select's decode-step form (outside the hot loop: waits for `hip_stream`): how many
+ * per-sequence selections since the context was created were resolved from the candidate list and how many by the
+ * slow single-block fallback.  Both are host int64. */
+kvtrim_status kvtrim_select_path_counts(kvtrim_ctx *ctx, int64_t *from_list_host, int64_t *fallback_host,
+                                        void *hip_stream);
 
 /* Stage 3 - variable-length per-(layer, head) caches, Sec. 4.2 "Implementation
  * details", realised as a stable stream compaction: segment g of dst holds the
@@ -435,9 +462,9 @@ kvtrim_status kvtrim_select_global_noalloc(const kvtrim_config *cfg, const kvtri
  * end waits for `hip_stream` and writes, per kernel id, the summed duration in
  * milliseconds and the number of bracketed launches into host arrays of
  * KVTRIM_N_KERNELS elements.  Do not capture a HIP graph while profiling is on. */
-#define KVTRIM_N_KERNELS 32
+#define KVTRIM_N_KERNELS 40
 #define KVTRIM_PROFILE_MAX_LAUNCHES 4096
-kvtrim_status kvtrim_profile_begin(kvtrim_ctx *ctx, uint32_t kernel_mask);
+kvtrim_status kvtrim_profile_begin(kvtrim_ctx *ctx, uint64_t kernel_mask);
 kvtrim_status kvtrim_profile_end(kvtrim_ctx *ctx, void *hip_stream, double *ms_sum_host,
                                  int64_t *launches_host);
 const char *kvtrim_kernel_name(int32_t kernel_id); /* NULL when out of range */

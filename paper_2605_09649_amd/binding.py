@@ -12,7 +12,7 @@ STATUS = {0: "KVTRIM_OK", -1: "KVTRIM_EINVAL", -2: "KVTRIM_ENOMEM", -3: "KVTRIM_
           -5: "KVTRIM_EMISMATCH", -6: "KVTRIM_ELAYOUT"}
 
 EXPORTS = ["kvtrim_create", "kvtrim_destroy", "kvtrim_workspace_bytes", "kvtrim_last_error",
-           "kvtrim_poll_error", "kvtrim_score", "kvtrim_select_global", "kvtrim_compact",
+           "kvtrim_poll_error", "kvtrim_score", "kvtrim_select_global", "kvtrim_score_select", "kvtrim_select_path_counts", "kvtrim_compact",
            "kvtrim_decode_attn", "kvtrim_decode_attn_soft", "kvtrim_occupancy", "kvtrim_compact_attn", "kvtrim_min_room", "kvtrim_compact_inplace", "kvtrim_compact_attn_inplace", "kvtrim_append", "kvtrim_append_compact",
            "kvtrim_paged_build", "kvtrim_paged_append", "kvtrim_paged_score", "kvtrim_paged_select",
            "kvtrim_paged_evict", "kvtrim_paged_defrag", "kvtrim_paged_attn", "kvtrim_gate_scratch_bytes", "kvtrim_gate_forward", "kvtrim_gate_prepared_bytes", "kvtrim_gate_prepare",
@@ -21,7 +21,7 @@ EXPORTS = ["kvtrim_create", "kvtrim_destroy", "kvtrim_workspace_bytes", "kvtrim_
            "kvtrim_profile_begin", "kvtrim_profile_end",
            "kvtrim_kernel_name"]
 PAGE_SIZE = 128
-N_KERNELS = 32
+N_KERNELS = 40
 
 
 class KvtrimError(RuntimeError):
@@ -75,6 +75,9 @@ def load_library():
         lib.kvtrim_score.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.c_void_p]
         lib.kvtrim_select_global.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.c_void_p,
                                              C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.kvtrim_score_select.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        lib.kvtrim_select_path_counts.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.c_void_p]
         lib.kvtrim_compact.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.POINTER(_Cache),
                                        C.c_int32, C.c_void_p]
         lib.kvtrim_decode_attn.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_int32, C.c_int32,
@@ -117,7 +120,7 @@ def load_library():
                                                      C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.kvtrim_select_global_noalloc.argtypes = [C.POINTER(_Config), C.POINTER(_Cache), C.c_void_p, C.c_void_p,
                                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
-        lib.kvtrim_profile_begin.argtypes = [C.c_void_p, C.c_uint32]
+        lib.kvtrim_profile_begin.argtypes = [C.c_void_p, C.c_uint64]
         lib.kvtrim_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         lib.kvtrim_kernel_name.argtypes = [C.c_int32]
         lib.kvtrim_kernel_name.restype = C.c_char_p
@@ -280,6 +283,21 @@ def kvtrim_select_global(ctx, cache, score, budget, keep_out, kept_out, thr_key_
         ctx.handle, C.byref(cache.c), _ptr(score, torch.float32), _ptr(budget, torch.int64),
         _ptr(keep_out, torch.uint8), _ptr(kept_out, torch.int32), _ptr(thr_key_out), _stream(stream)),
         "kvtrim_select_global")
+
+
+def kvtrim_score_select(ctx, cache, now, budget, score_out, keep_out, kept_out, thr_key_out=None, evict_hint=0, stream=None):
+    _check(ctx, load_library().kvtrim_score_select(
+        ctx.handle, C.byref(cache.c), _ptr(now, torch.int32), _ptr(budget, torch.int64), _ptr(score_out, torch.float32),
+        _ptr(keep_out, torch.uint8), _ptr(kept_out, torch.int32), _ptr(thr_key_out), int(evict_hint), _stream(stream)),
+        "kvtrim_score_select")
+
+
+def kvtrim_select_path_counts(ctx, stream=None):
+    """(selections resolved from the candidate list, selections resolved by the single-block fallback)."""
+    a, b = C.c_int64(), C.c_int64()
+    _check(ctx, load_library().kvtrim_select_path_counts(ctx.handle, C.byref(a), C.byref(b), _stream(stream)),
+           "kvtrim_select_path_counts")
+    return int(a.value), int(b.value)
 
 
 def kvtrim_select_global_noalloc(config, cache, score, budget, keep_out, kept_out, thr_key_out=None, status_out=None,

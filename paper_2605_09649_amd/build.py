@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvtrim.so")
-SOURCES = ["kvtrim_api.hip", "kvtrim_noalloc.hip", "k_score.hip", "k_select.hip", "k_compact.hip", "k_attn.hip", "k_fused.hip", "k_paged.hip", "k_gate.hip"]
+SOURCES = ["kvtrim_api.hip", "kvtrim_noalloc.hip", "k_score.hip", "k_select.hip", "k_fastsel.hip", "k_compact.hip", "k_attn.hip", "k_fused.hip", "k_paged.hip", "k_gate.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

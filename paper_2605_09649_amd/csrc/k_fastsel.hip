@@ -1,0 +1,642 @@
+// Stages 1 + 2 for decode steps (Sec. 4.2: Eq. global_score and the global eviction rule) in two kernels.
+//
+// A decode step evicts a handful of entries per sequence - as many as it appended - so the selection is the
+// search for the FEW LOWEST entries of the total order (key descending, segment ascending, position ascending),
+// not a general top-B.  The pass that computes the scores lists every entry whose key lies below a bound `hi`
+// carried over from the previous call; if the list holds at least k + 1 entries (k = count - min(budget, count)
+// evictions), the k + 1 lowest entries of the whole sequence are the k + 1 lowest of the list, because every entry
+// that is not listed has a key >= hi > every listed key.  The last block to finish a sequence ("last block done",
+// one arrival counter per sequence) ranks the list - a few hundred entries - and publishes the last retained
+// entry of the order as (key, segment, position); the mask kernel compares every entry with that triple.
+//
+// The bound adapts by itself: the next bound is the key of about the 3(k+1)-th lowest entry of the current
+// list.  Scores only decay from step to step (beta <= 1, Eq. global_score) and new tokens enter with the highest
+// scores, so the 2(k+1) retained entries below that key are below it at the next step as well: with a steady
+// number of evictions per step the list can never come up short.  Nothing depends on the bound for correctness:
+// a list that is short (first call, a budget or workload change), too long for its buffer, or with too many equal
+// keys at the threshold makes the last block run a plain three-pass radix select over the sequence on its own
+// (slow - one block reads every score three times - but rare) which also re-seeds the bound.
+#include "kvtrim_device.h"
+
+namespace kvtrim {
+
+constexpr int FAST_ITEMS = FL_CAP_MAX / FAST_THREADS;             // list entries a thread of the resolving block holds
+constexpr int FAST_SUB = 16;                                      // sub-lists / group words per sequence
+constexpr int FAST_STAGE = 1024;                                  // candidates a block stages in LDS
+constexpr int FAST_BATCH = 8;                                     // entries a thread loads before it uses any of them
+constexpr int FAST_BIN_DIRECT = 256;                              // a bin of at most this many entries is ranked directly
+static_assert(FAST_ITEMS * FAST_THREADS == FL_CAP_MAX, "list capacity must be a multiple of the block size");
+
+// Length of segment g, or 0 with *bad set when its table entry is unusable (negative, beyond the buffers, or
+// overlapping its successor).  Every kernel of this file sees a segment through this function.
+__device__ __forceinline__ int seg_checked_len(const CacheView& c, int g, int nseg, int64_t* start, bool* bad) {
+    const int len = c.seg_len[g];
+    const int64_t st = c.seg_start[g];
+    const int64_t nxt = g + 1 < nseg ? c.seg_start[g + 1] : c.cap;
+    *start = st;
+    if (len < 0 || st < 0 || st + len > c.cap || st + len > nxt) {
+        *bad = true;
+        return 0;
+    }
+    return len;
+}
+
+// a is evicted before b: lower key first; among equal keys the later (segment, position) first
+__device__ __forceinline__ bool evicted_before(uint32_t ka, int sa, int pa, uint32_t kb, int sb, int pb) {
+    if (ka != kb) return ka < kb;
+    if (sa != sb) return sa > sb;
+    return pa > pb;
+}
+
+struct ResolveShared {
+    uint32_t h[2048];
+    int64_t lds64[17];
+    int32_t lds32[17];
+    uint32_t red_u[16];
+    int bin, bin_m, cnt, gather_n, found_seg, found_pos, digit;
+    int64_t before, rank_in;
+    uint32_t found_key, bin_count;
+    uint32_t g_key[FAST_BIN_DIRECT];
+    int32_t g_seg[FAST_BIN_DIRECT], g_pos[FAST_BIN_DIRECT];
+};
+
+__device__ __forceinline__ uint32_t block_min_u32(uint32_t v, uint32_t* red) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v = min(v, (uint32_t)__shfl_xor((int)v, d, 64));
+    __syncthreads();
+    if (lane_id() == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    uint32_t r = 0xFFFFFFFFu;
+    for (int i = 0; i < (int)(blockDim.x >> 6); ++i) r = min(r, red[i]);
+    return r;
+}
+
+__device__ __forceinline__ uint32_t block_max_u32(uint32_t v, uint32_t* red) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v = max(v, (uint32_t)__shfl_xor((int)v, d, 64));
+    __syncthreads();
+    if (lane_id() == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    uint32_t r = 0;
+    for (int i = 0; i < (int)(blockDim.x >> 6); ++i) r = max(r, red[i]);
+    return r;
+}
+
+// Walks an LDS histogram of NB bins from the top bin down to the one that holds the entry of rank `rank`
+// (1-based, descending digit order).  Results in sm->digit, sm->rank_in (rank inside the bin), sm->bin_count.
+template <int NB>
+__device__ __forceinline__ void walk_from_top(ResolveShared* sm, int64_t rank) {
+    constexpr int PER = NB / FAST_THREADS;                        // 2 or 1 bins per thread, thread 0 owns the highest
+    const int tid = threadIdx.x;
+    uint32_t cnt[PER];
+    int64_t mine = 0;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        cnt[i] = sm->h[NB - 1 - (tid * PER + i)];
+        mine += cnt[i];
+    }
+    int64_t tot;
+    int64_t above = block_excl_scan<int64_t>(mine, sm->lds64, &tot);
+    if (above < rank && rank <= above + mine) {
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            if (rank <= above + cnt[i]) {
+                sm->digit = NB - 1 - (tid * PER + i);
+                sm->rank_in = rank - above;
+                sm->bin_count = cnt[i];
+                break;
+            }
+            above += cnt[i];
+        }
+    }
+    __syncthreads();
+}
+
+// Where the key of an entry comes from: computed from log beta and the position (SCORE: stage 1 fused, Eq.
+// global_score in log domain - one fp32 multiply, or one fused multiply-add with the cached horizon tail) or
+// read from the caller's score array.  Both are inputs of the call, so any block may read any entry at any time.
+template <bool SCORE>
+struct KeySource {
+    const float* score_in;
+    const float* lb;
+    const float* lt;
+    const int32_t* pos;
+    int t1;
+    __device__ __forceinline__ float score_at(int64_t e) const {
+        if (!SCORE) return score_in[e];
+        const float dt = (float)(t1 - pos[e]);
+        return lt ? __fmaf_rn(dt, lb[e], lt[e]) : __fmul_rn(dt, lb[e]);
+    }
+};
+
+// One digit of a most-significant-digit radix select over all entries of the sequence, by this block alone.
+template <int PASS, bool SCORE>
+__device__ __forceinline__ void slow_pass(const KeySource<SCORE>& ks, const CacheView& c, const Shape& sh, int seq,
+                                          uint32_t prefix, ResolveShared* sm) {
+    constexpr int NB = PASS == 2 ? 1024 : 2048;
+    const int tid = threadIdx.x;
+    __syncthreads();
+    for (int i = tid; i < NB; i += FAST_THREADS) sm->h[i] = 0;
+    __syncthreads();
+    for (int g = seq * sh.segs_per_seq; g < (seq + 1) * sh.segs_per_seq; ++g) {
+        int64_t start;
+        bool bad = false;
+        const int len = seg_checked_len(c, g, sh.nseg, &start, &bad);
+        for (int j0 = tid; j0 < len; j0 += FAST_THREADS * FAST_BATCH) {
+            float sv[FAST_BATCH];
+#pragma unroll
+            for (int u = 0; u < FAST_BATCH; ++u) {
+                const int j = j0 + u * FAST_THREADS;
+                sv[u] = j < len ? ks.score_at(start + j) : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < FAST_BATCH; ++u) {
+                int bin;
+                if (j0 + u * FAST_THREADS < len && digit_of<PASS>(key_of_score(sv[u]), prefix, &bin)) atomicAdd(&sm->h[bin], 1u);
+            }
+        }
+    }
+    __syncthreads();
+}
+
+// Key of the entry of rank `rank` (1-based, descending key order) of the sequence; *rank_in = its rank among the
+// entries with that key, *ties = how many entries have that key.
+template <bool SCORE>
+__device__ __forceinline__ uint32_t slow_radix(const KeySource<SCORE>& ks, const CacheView& c, const Shape& sh,
+                                               int seq, int64_t rank, ResolveShared* sm, int64_t* rank_in,
+                                               uint32_t* ties) {
+    slow_pass<0>(ks, c, sh, seq, 0, sm);
+    walk_from_top<2048>(sm, rank);
+    uint32_t prefix = (uint32_t)sm->digit;
+    rank = sm->rank_in;
+    slow_pass<1>(ks, c, sh, seq, prefix, sm);
+    walk_from_top<2048>(sm, rank);
+    prefix = (prefix << RADIX_BITS1) | (uint32_t)sm->digit;
+    rank = sm->rank_in;
+    slow_pass<2>(ks, c, sh, seq, prefix, sm);
+    walk_from_top<1024>(sm, rank);
+    prefix = (prefix << RADIX_BITS2) | (uint32_t)sm->digit;
+    *rank_in = sm->rank_in;
+    *ties = sm->bin_count;
+    __syncthreads();
+    return prefix;
+}
+
+// The `quota`-th entry (1-based) with key == key_thr in (segment ascending, position ascending) order:
+// result in sm->found_seg / sm->found_pos.  The caller guarantees that it exists.
+template <bool SCORE>
+__device__ __forceinline__ void slow_tie_walk(const KeySource<SCORE>& ks, const CacheView& c, const Shape& sh,
+                                              int seq, uint32_t key_thr, int64_t quota, ResolveShared* sm) {
+    const int tid = threadIdx.x;
+    int64_t need = quota;
+    for (int g = seq * sh.segs_per_seq; g < (seq + 1) * sh.segs_per_seq; ++g) {
+        int64_t start;
+        bool bad = false;
+        const int len = seg_checked_len(c, g, sh.nseg, &start, &bad);
+        int mine = 0;
+        for (int j = tid; j < len; j += FAST_THREADS) mine += key_of_score(ks.score_at(start + j)) == key_thr;
+        const int in_seg = block_sum<int32_t>(mine, sm->lds32);
+        if (need > in_seg) {
+            need -= in_seg;
+            continue;
+        }
+        // the entry is in this segment: entries are stored in position order
+        int64_t running = 0;
+        for (int base = 0; base < len; base += FAST_THREADS) {    // uniform trip count
+            const int j = base + tid;
+            const int is_eq = j < len && key_of_score(ks.score_at(start + j)) == key_thr;
+            int32_t tot;
+            const int32_t ex = block_excl_scan<int32_t>(is_eq, sm->lds32, &tot);
+            if (is_eq && running + ex == need - 1) {
+                sm->found_seg = g;
+                sm->found_pos = c.pos[start + j];
+            }
+            running += tot;
+            if (running >= need) break;                           // uniform: tot comes from LDS
+        }
+        __syncthreads();
+        return;
+    }
+    __syncthreads();
+}
+
+// loads and stores that bypass the caches which are not coherent across the chip (what one block writes this way
+// and has seen acknowledged, another block reads this way without any fence)
+template <typename T>
+__device__ __forceinline__ T ld_dev(const T* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+template <typename T>
+__device__ __forceinline__ void st_dev(T* p, T v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
+// SCORE: stage 1 is computed here (and written to score_out); otherwise the scores are read from score_in.
+//
+// Cross-block traffic inside the kernel: the candidate lists, their counters, the lowest keys and the arrival
+// counters.  All of it is written with device-scope atomics or write-through stores whose acknowledgement the
+// writer waits for before it arrives, and read with device-scope loads - so no block needs a fence, which on this
+// chip means a write-back of a whole L2.  The scores written here are read by the NEXT kernel only; the
+// single-block select, which has to look at every entry, recomputes them from the call's inputs.
+template <bool SCORE>
+__global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const int32_t* __restrict__ now,
+                                                            const float* score_in, float* score_out,
+                                                            const int64_t* __restrict__ budget, Shape sh, Workspace ws,
+                                                            int bps, int32_t* __restrict__ kept_out,
+                                                            uint32_t* __restrict__ thr_out) {
+    __shared__ ResolveShared sm;
+    __shared__ int s_last, s_ncand;
+    __shared__ uint32_t s_base;
+    __shared__ uint32_t c_key[FAST_STAGE];                        // this block's candidates, before they go to the list
+    __shared__ int32_t c_pos[FAST_STAGE];
+    const int tid = threadIdx.x;
+    const int seg = blockIdx.x / bps, part = blockIdx.x % bps;
+    const int seq = seg / sh.segs_per_seq;
+    // Device-scope atomics on one address are served one after the other (tens of nanoseconds each), so the
+    // blocks of a sequence do not meet on one word: the list is kept in up to FAST_SUB sub-lists with a counter
+    // each, the lowest key and the arrivals in FAST_SUB group words (then one top-level arrival per group).
+    const int blk_in_seq = (seg - seq * sh.segs_per_seq) * bps + part;
+    const int nblk = sh.segs_per_seq * bps;
+    const int nsub = nblk < FAST_SUB ? nblk : FAST_SUB;
+    const int sub = blk_in_seq % nsub;
+    if (tid == 0) s_ncand = 0;
+    __syncthreads();
+    int64_t start;
+    bool bad = false;
+    const int len = seg_checked_len(c, seg, sh.nseg, &start, &bad);
+    if (bad && tid == 0 && part == 0) atomicOr(ws.err, ERR_LAYOUT);
+    const uint32_t hi = ws.fast_hi[seq];
+    const uint32_t cap = (uint32_t)ws.fl_cap;
+    const uint32_t subcap = cap / (uint32_t)nsub;                 // entries per sub-list
+    uint32_t* lk = ws.fl_key + (size_t)seq * cap;
+    int32_t* ls = ws.fl_seg + (size_t)seq * cap;
+    int32_t* lp = ws.fl_pos + (size_t)seq * cap;
+    uint32_t* sub_count = ws.fl_count + (size_t)seq * FAST_SUB;
+    uint32_t* grp_min = ws.fast_min + (size_t)seq * FAST_SUB;
+    uint32_t* done = ws.fast_done + (size_t)seq * (FAST_SUB + 1);
+    KeySource<SCORE> ks;
+    ks.score_in = score_in;
+    ks.lb = c.log_beta;
+    ks.lt = c.log_tail;
+    ks.pos = c.pos;
+    ks.t1 = SCORE ? now[seq] + 1 : 0;
+
+    // ---- every entry of this block's share: score, and onto the list if its key is below the bound
+    {
+        const int32_t* pos = c.pos + start;
+        uint32_t mn = 0xFFFFFFFFu;
+        // batches of FAST_BATCH entries per thread: all loads of a batch are issued before any of them is used
+        for (int j0 = part * FAST_THREADS + tid; j0 < len; j0 += bps * FAST_THREADS * FAST_BATCH) {
+            float sv[FAST_BATCH];
+            int pv[FAST_BATCH];
+            if (SCORE) {
+                const float* lb = c.log_beta + start;
+                const float* lt = c.log_tail ? c.log_tail + start : nullptr;
+                float lbv[FAST_BATCH], ltv[FAST_BATCH];
+#pragma unroll
+                for (int u = 0; u < FAST_BATCH; ++u) {
+                    const int j = j0 + u * bps * FAST_THREADS;
+                    const bool in = j < len;
+                    pv[u] = in ? pos[j] : 0;
+                    lbv[u] = in ? lb[j] : 0.f;
+                    ltv[u] = (in && lt) ? lt[j] : 0.f;
+                }
+#pragma unroll
+                for (int u = 0; u < FAST_BATCH; ++u) {
+                    const int j = j0 + u * bps * FAST_THREADS;
+                    const float dt = (float)(ks.t1 - pv[u]);
+                    sv[u] = lt ? __fmaf_rn(dt, lbv[u], ltv[u]) : __fmul_rn(dt, lbv[u]);
+                    if (j < len) score_out[start + j] = sv[u];
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < FAST_BATCH; ++u) {
+                    const int j = j0 + u * bps * FAST_THREADS;
+                    sv[u] = j < len ? score_in[start + j] : 0.f;
+                    pv[u] = 0;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < FAST_BATCH; ++u) {
+                const int j = j0 + u * bps * FAST_THREADS;
+                const uint32_t key = key_of_score(sv[u]);
+                if (j < len) mn = min(mn, key);
+                if (j < len && key < hi) {                        // rare: a few hundred entries per sequence and call
+                    const int slot = atomicAdd(&s_ncand, 1);
+                    if (slot < FAST_STAGE) {
+                        c_key[slot] = key;
+                        c_pos[slot] = SCORE ? pv[u] : pos[j];
+                    }
+                }
+            }
+        }
+        mn = block_min_u32(mn, sm.red_u);                         // (its barriers also complete s_ncand and the staged entries)
+        const int ncand = s_ncand;
+        if (tid == 0) {
+            if (mn != 0xFFFFFFFFu) atomicMin(&grp_min[sub], mn);
+            // one reservation per block; a block with more candidates than it can stage makes its sub-list overflow
+            if (ncand > 0) s_base = atomicAdd(&sub_count[sub], ncand > FAST_STAGE ? cap + 1u : (uint32_t)ncand);
+        }
+        __syncthreads();
+        if (ncand > 0 && ncand <= FAST_STAGE) {
+            const uint32_t base = s_base;
+            for (int i = tid; i < ncand; i += FAST_THREADS) {
+                const uint32_t slot = base + (uint32_t)i;
+                if (slot < subcap) {
+                    const size_t at = (size_t)sub * subcap + slot;
+                    st_dev(&lk[at], c_key[i]);
+                    st_dev(&ls[at], (int32_t)seg);
+                    st_dev(&lp[at], c_pos[i]);
+                }
+            }
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");              // this thread's list entries are acknowledged ...
+    __syncthreads();                                              // ... and so are the whole block's, before it arrives
+    if (tid == 0) {
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");   // (thread 0's own atomics above have returned)
+        const int grp = blk_in_seq % FAST_SUB;
+        const unsigned gsize = (unsigned)(nblk - grp + FAST_SUB - 1) / FAST_SUB;   // blocks of the sequence with this group number
+        int last = 0;
+        if (atomicAdd(&done[1 + grp], 1u) == gsize - 1u) {
+            const unsigned ngroups = nblk < FAST_SUB ? (unsigned)nblk : (unsigned)FAST_SUB;
+            last = atomicAdd(&done[0], 1u) == ngroups - 1u;
+        }
+        s_last = last;
+    }
+    __syncthreads();
+    if (!s_last) return;
+
+    // ---- the last block of the sequence: everything of the sequence has been scored and listed.
+    // All it needs is requested at once: the sub-list counters, the lowest keys, every slot of the list (whether
+    // a slot holds an entry is known once the counters are here), the segment lengths, the budget.
+    uint32_t sub_n[FAST_SUB];
+    uint32_t min_key = 0xFFFFFFFFu;
+#pragma unroll
+    for (int i = 0; i < FAST_SUB; ++i) {
+        sub_n[i] = i < nsub ? ld_dev(&sub_count[i]) : 0u;
+        min_key = min(min_key, ld_dev(&grp_min[i]));
+    }
+    uint32_t key[FAST_ITEMS];
+    int sg[FAST_ITEMS], ps[FAST_ITEMS];
+    uint32_t slot_sub[FAST_ITEMS], slot_idx[FAST_ITEMS];
+#pragma unroll
+    for (int u = 0; u < FAST_ITEMS; ++u) {
+        const uint32_t i = (uint32_t)tid + (uint32_t)u * FAST_THREADS;   // slot i of the flat list buffer
+        slot_sub[u] = i / subcap;
+        slot_idx[u] = i - slot_sub[u] * subcap;
+        key[u] = 0;
+        sg[u] = ps[u] = 0;
+        if (i < cap && slot_sub[u] < (uint32_t)nsub) {
+            key[u] = ld_dev(&lk[i]);
+            sg[u] = ld_dev(&ls[i]);
+            ps[u] = ld_dev(&lp[i]);
+        }
+    }
+    const int g0 = seq * sh.segs_per_seq;
+    int64_t cnt = 0;
+    for (int g = g0 + tid; g < g0 + sh.segs_per_seq; g += FAST_THREADS) {
+        int64_t st;
+        bool b2 = false;
+        cnt += seg_checked_len(c, g, sh.nseg, &st, &b2);
+        kept_out[g] = 0;                                          // the mask kernel adds its counts
+    }
+    int64_t bud = budget[seq];
+    if (bud < 0) bud = 0;
+    bool sub_overflow = false;
+    uint32_t n_list = 0;
+#pragma unroll
+    for (int i = 0; i < FAST_SUB; ++i) {
+        sub_overflow = sub_overflow || sub_n[i] > subcap;
+        n_list += sub_n[i] > subcap ? subcap : sub_n[i];
+    }
+    bool valid[FAST_ITEMS];
+    uint32_t lo = 0xFFFFFFFFu, hi_k = 0;
+#pragma unroll
+    for (int u = 0; u < FAST_ITEMS; ++u) {
+        uint32_t n_here = 0;
+#pragma unroll
+        for (int q = 0; q < FAST_SUB; ++q) n_here = slot_sub[u] == (uint32_t)q ? sub_n[q] : n_here;
+        valid[u] = (uint32_t)tid + (uint32_t)u * FAST_THREADS < cap && slot_sub[u] < (uint32_t)nsub && slot_idx[u] < n_here;
+        if (valid[u]) {
+            lo = min(lo, key[u]);
+            hi_k = max(hi_k, key[u]);
+        }
+    }
+    __syncthreads();                                              // every thread has read the per-call words
+    if (tid <= FAST_SUB) {                                        // ... which go back to "between calls"
+        atomicExch(&done[tid], 0u);
+        if (tid < FAST_SUB) {
+            atomicExch(&sub_count[tid], 0u);
+            atomicExch(&grp_min[tid], 0xFFFFFFFFu);
+        }
+    }
+    {   // entries of the sequence, lowest and highest listed key: one reduction
+        cnt = wave_sum(cnt);
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            lo = min(lo, (uint32_t)__shfl_xor((int)lo, d, 64));
+            hi_k = max(hi_k, (uint32_t)__shfl_xor((int)hi_k, d, 64));
+        }
+        if (lane_id() == 0) {
+            sm.lds64[tid >> 6] = cnt;
+            sm.red_u[tid >> 6] = lo;
+            sm.h[tid >> 6] = hi_k;
+        }
+        __syncthreads();
+        cnt = 0;
+        for (int i = 0; i < FAST_THREADS / 64; ++i) {
+            cnt += sm.lds64[i];
+            lo = min(lo, sm.red_u[i]);
+            hi_k = max(hi_k, sm.h[i]);
+        }
+    }
+    const int64_t want = bud < cnt ? bud : cnt;
+    const int64_t k = cnt - want;                                 // entries to evict
+    FastSel out;
+    out.mode = FSEL_THRESHOLD;
+    out.key_thr = 0xFFFFFFFFu;
+    out.seg_thr = 0x7fffffff;
+    out.pos_thr = 0x7fffffff;
+    uint32_t next_hi = hi;
+    bool used_fallback = false;
+    if (want == 0) {
+        out.mode = FSEL_NONE;
+    } else if (k == 0) {
+        out.mode = FSEL_ALL;
+        out.key_thr = min_key;                                    // key of the last entry of the order
+    } else {
+        bool solved = false;
+        if (!sub_overflow && (int64_t)n_list >= k + 1 && n_list <= cap) {
+            // -- rank the list: the entry of rank k (0-based, eviction order) is the last retained one
+            int64_t r = k;
+            bool first = true;
+            for (int round = 0; round < 5; ++round) {             // every round narrows the key range by a factor of 1024
+                const uint32_t range = hi_k - lo;
+                const int shift = range < 1024u ? 0 : 32 - __clz(range) - 10;
+                __syncthreads();
+                sm.h[tid] = 0;
+                if (tid == 0) sm.gather_n = 0;
+                __syncthreads();
+#pragma unroll
+                for (int u = 0; u < FAST_ITEMS; ++u)
+                    if (valid[u]) atomicAdd(&sm.h[(key[u] - lo) >> shift], 1u);
+                __syncthreads();
+                const int32_t v = (int32_t)sm.h[tid];
+                int32_t tot;
+                const int32_t ex = block_excl_scan<int32_t>(v, sm.lds32, &tot);
+                if (ex <= r && r < (int64_t)ex + v) {
+                    sm.bin = tid;
+                    sm.before = ex;
+                    sm.cnt = v;
+                }
+                if (first) {
+                    const int64_t m3 = 3 * (k + 1);
+                    const int64_t m = m3 < (int64_t)tot - 1 ? m3 : (int64_t)tot - 1;
+                    if (ex <= m && m < (int64_t)ex + v) sm.bin_m = tid;
+                }
+                __syncthreads();
+                const int bin = sm.bin, bcnt = sm.cnt;
+                const int64_t before = sm.before;
+                if (first) {
+                    // next bound: the upper edge of the bin that holds the entry of rank min(3(k+1), n - 1);
+                    // doubled distance from the threshold's bin when the list was too short to reach that rank
+                    uint64_t edge = (uint64_t)lo + (((uint64_t)sm.bin_m + 1) << shift);
+                    if ((int64_t)tot - 1 < 3 * (k + 1)) edge += edge - ((uint64_t)lo + ((uint64_t)bin << shift));
+                    next_hi = edge > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)edge;
+                    first = false;
+                }
+                if (bcnt <= FAST_BIN_DIRECT) {
+                    // few entries in the bin: rank them directly on the whole triple
+#pragma unroll
+                    for (int u = 0; u < FAST_ITEMS; ++u) {
+                        if (valid[u] && (int)((key[u] - lo) >> shift) == bin) {
+                            const int slot = atomicAdd(&sm.gather_n, 1);
+                            sm.g_key[slot] = key[u];
+                            sm.g_seg[slot] = sg[u];
+                            sm.g_pos[slot] = ps[u];
+                        }
+                    }
+                    __syncthreads();
+                    if (tid < bcnt) {
+                        const uint32_t mk = sm.g_key[tid];
+                        const int ms = sm.g_seg[tid], mp = sm.g_pos[tid];
+                        int rank = 0;
+                        for (int j = 0; j < bcnt; ++j) rank += evicted_before(sm.g_key[j], sm.g_seg[j], sm.g_pos[j], mk, ms, mp);
+                        if (rank == (int)(r - before)) {
+                            sm.found_key = mk;
+                            sm.found_seg = ms;
+                            sm.found_pos = mp;
+                        }
+                    }
+                    __syncthreads();
+                    out.key_thr = sm.found_key;
+                    out.seg_thr = sm.found_seg;
+                    out.pos_thr = sm.found_pos;
+                    solved = true;
+                    break;
+                }
+                if (shift == 0) break;                            // too many equal keys at the threshold: the plain select below
+                const uint32_t nlo = lo + ((uint32_t)bin << shift);
+#pragma unroll
+                for (int u = 0; u < FAST_ITEMS; ++u) valid[u] = valid[u] && (int)((key[u] - lo) >> shift) == bin;
+                lo = nlo;
+                const uint64_t top = (uint64_t)nlo + ((1ull << shift) - 1ull);
+                hi_k = top < (uint64_t)hi_k ? (uint32_t)top : hi_k;
+                r -= before;
+            }
+        }
+        if (!solved) {
+            // -- plain radix select by this block alone; also the bound for the next call
+            used_fallback = true;
+            __syncthreads();
+            int64_t rank_in;
+            uint32_t ties;
+            const uint32_t key_thr = slow_radix(ks, c, sh, seq, want, &sm, &rank_in, &ties);
+            out.key_thr = key_thr;
+            if (rank_in < (int64_t)ties) {                        // only the first rank_in of the equal keys survive
+                slow_tie_walk(ks, c, sh, seq, key_thr, rank_in, &sm);
+                out.seg_thr = sm.found_seg;
+                out.pos_thr = sm.found_pos;
+            }
+            __syncthreads();
+            const int64_t above = seed_distance(k, sh.segs_per_seq, ws.fl_cap);
+            const int64_t rank_b = want - above >= 1 ? want - above : 1;
+            int64_t unused_r;
+            uint32_t unused_t;
+            const uint32_t key_b = slow_radix(ks, c, sh, seq, rank_b, &sm, &unused_r, &unused_t);
+            next_hi = key_b == 0xFFFFFFFFu ? key_b : key_b + 1u;
+        }
+    }
+    if (tid == 0) {
+        if (out.mode == FSEL_THRESHOLD) atomicAdd(&ws.fast_stat[used_fallback ? 1 : 0], 1ull);
+        ws.fast_sel[seq] = out;
+        if (thr_out) thr_out[seq] = out.mode == FSEL_NONE ? 0xFFFFFFFFu : out.key_thr;
+        if (out.mode == FSEL_THRESHOLD) ws.fast_hi[seq] = next_hi;
+    }
+}
+
+// keep[e] from the published triple; survivors per segment are added to kept_out (zeroed by k_fast_scan).
+__global__ __launch_bounds__(FAST_THREADS) void k_fast_mask(CacheView c, const float* __restrict__ score, Shape sh,
+                                                            Workspace ws, int bps, uint8_t* __restrict__ keep,
+                                                            int32_t* __restrict__ kept_out) {
+    __shared__ int32_t lds32[17];
+    const int tid = threadIdx.x;
+    const int seg = blockIdx.x / bps, part = blockIdx.x % bps;
+    const int seq = seg / sh.segs_per_seq;
+    int64_t start;
+    bool bad = false;
+    const int len = seg_checked_len(c, seg, sh.nseg, &start, &bad);
+    const FastSel fs = ws.fast_sel[seq];
+    const float* s = score + start;
+    const int32_t* pos = c.pos + start;
+    uint8_t* kp = keep + start;
+    int n = 0;
+    if (fs.mode != FSEL_THRESHOLD) {
+        const uint8_t v = fs.mode == FSEL_ALL;
+        for (int j = part * FAST_THREADS + tid; j < len; j += bps * FAST_THREADS) {
+            kp[j] = v;
+            n += v;
+        }
+    } else {
+        const bool seg_before = seg < fs.seg_thr, seg_same = seg == fs.seg_thr;
+        for (int j0 = part * FAST_THREADS + tid; j0 < len; j0 += bps * FAST_THREADS * FAST_BATCH) {
+            float sv[FAST_BATCH];
+#pragma unroll
+            for (int u = 0; u < FAST_BATCH; ++u) {
+                const int j = j0 + u * bps * FAST_THREADS;
+                sv[u] = j < len ? s[j] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < FAST_BATCH; ++u) {
+                const int j = j0 + u * bps * FAST_THREADS;
+                if (j < len) {
+                    const uint32_t key = key_of_score(sv[u]);
+                    bool kf = key > fs.key_thr;
+                    if (key == fs.key_thr) kf = seg_before || (seg_same && pos[j] <= fs.pos_thr);
+                    kp[j] = kf;
+                    n += kf;
+                }
+            }
+        }
+    }
+    n = block_sum<int32_t>(n, lds32);
+    if (tid == 0 && n) atomicAdd(&kept_out[seg], n);
+}
+
+kvtrim_status launch_score_select(kvtrim_ctx* ctx, const CacheView& c, const int32_t* now, const int64_t* budget,
+                                  float* score, uint8_t* keep, int32_t* kept, uint32_t* thr, int64_t evict_hint,
+                                  hipStream_t st) {
+    const Shape& sh = ctx->shape;
+    const Workspace& ws = ctx->ws;
+    // the list has to hold about 3 (k + 1) entries for k evictions, spread unevenly over its sub-lists
+    if (evict_hint <= 0 || 8 * (evict_hint + 1) > (int64_t)ws.fl_cap)
+        return launch_score_select_general(ctx, c, now, budget, score, keep, kept, thr, st);
+    int64_t bps = c.cap / ((int64_t)sh.nseg * FAST_ENTRIES_PER_BLOCK);
+    bps = bps < 1 ? 1 : (bps > 64 ? 64 : bps);
+    const dim3 grid((unsigned)(sh.nseg * bps)), block(FAST_THREADS);
+    { ProfScope prof(ctx, K_FAST_SCAN, st);
+      hipLaunchKernelGGL(k_fast_scan<true>, grid, block, 0, st, c, now, (const float*)nullptr, score, budget, sh, ws, (int)bps, kept, thr); }
+    { ProfScope prof(ctx, K_FAST_MASK, st);
+      hipLaunchKernelGGL(k_fast_mask, grid, block, 0, st, c, (const float*)score, sh, ws, (int)bps, keep, kept); }
+    KVTRIM_HIP(ctx, hipGetLastError());
+    return KVTRIM_OK;
+}
+
+}  // namespace kvtrim

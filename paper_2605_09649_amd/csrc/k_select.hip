@@ -1,9 +1,14 @@
-// Stage 2: one global top-B selection per sequence (Sec. 4.2, eviction rule).
+// Stage 2: one global top-B selection per sequence (Sec. 4.2, eviction rule) - the general form, for any
+// number of evictions (the decode-step form, which looks only for the few lowest entries, is in k_fastsel.hip).
 //
 // Exact selection by a three-pass most-significant-digit radix select (11 + 11 + 10 bits)
 // on the order-preserving uint32 image of the fp32 score.  Each pass builds per-block
-// histograms in LDS, merges them with device-scope atomics, and the last block to finish
-// walks the merged histogram from the top to fix the next digits of the threshold key.
+// histograms in LDS and merges them with device-scope atomics into replicated global histograms.
+// Every block of pass p + 1 finds the digit of pass p itself, by walking the merged histogram of
+// pass p in its prologue; only the last pass uses "last block done" (per sequence: the last block
+// that holds entries of the sequence fixes the final digit, the threshold key and the tie quota).
+// The first pass can compute the score on the fly (stage 1 fused: it reads log beta and the
+// position instead of a score array and writes the score out as it goes).
 // Entries above the threshold are kept; entries equal to it are kept in storage order
 // (segment ascending, position ascending = layer, head, position) until the budget is
 // met.  When every entry equal to the threshold fits (the usual case) the mask is a plain
@@ -115,10 +120,15 @@ __device__ __forceinline__ SelState next_digit(const uint32_t* __restrict__ hist
 // write-back each and dominated the pass).
 // SHIFT = log2 of the chunk size of the table (2048-entry chunks of a ragged cache, 128-slot pages of a
 // paged one); PAGED: a slot counts only if its position is not negative.
-template <int PASS, int SHIFT, bool PAGED>
+// SCORE (first pass of a ragged cache only): the score is computed here from log beta and the position (Eq.
+// global_score in log domain, exactly as k_score does) and written to score_w; `score` is not read.
+template <int PASS, int SHIFT, bool PAGED, bool SCORE = false>
 __global__ __launch_bounds__(HIST_THREADS) void k_sel_hist(const float* __restrict__ score, Shape sh,
                                                            Workspace ws, SelTables tb,
-                                                           uint32_t* __restrict__ thr_out) {
+                                                           uint32_t* __restrict__ thr_out, CacheView c,
+                                                           const int32_t* __restrict__ now,
+                                                           float* __restrict__ score_w) {
+    static_assert(!SCORE || (PASS == 0 && !PAGED), "the score is fused into the first pass over a ragged cache only");
     constexpr int NB = PASS == 2 ? 1024 : 2048;
     constexpr int HIST_TILE = 64;
     __shared__ uint32_t h[NB];
@@ -140,7 +150,8 @@ __global__ __launch_bounds__(HIST_THREADS) void k_sel_hist(const float* __restri
             const int a = max(c0, tb.prefix[seq * sh.segs_per_seq]);
             const int b = min(c1, tb.prefix[(seq + 1) * sh.segs_per_seq]);
             if (a >= b) continue;
-            if (ws.sel[seq].keep_none) continue;
+            if (!SCORE && ws.sel[seq].keep_none) continue;        // (with SCORE the pass still has the scores to write)
+            const int t1 = SCORE ? now[seq] + 1 : 0;
             // The digits fixed so far: every block derives them itself from the previous pass's merged histogram
             // (a few microseconds of L2 reads, the same for all blocks) instead of waiting for that pass's last
             // block to do it, which put "last block done" detection and the walk on the critical path of every pass.
@@ -191,7 +202,16 @@ __global__ __launch_bounds__(HIST_THREADS) void k_sel_hist(const float* __restri
                         const int j = slot & ((1 << SHIFT) - 1);
                         if (j < d.n) {
                             int bin;
-                            if (digit_of<PASS>(key_of_score(score[d.first + j]), prefix, &bin)) atomicAdd(&h[bin], 1u);
+                            float sv;
+                            if (SCORE) {
+                                const int64_t e = d.first + j;
+                                const float dt = (float)(t1 - c.pos[e]);
+                                sv = c.log_tail ? __fmaf_rn(dt, c.log_beta[e], c.log_tail[e]) : __fmul_rn(dt, c.log_beta[e]);
+                                score_w[e] = sv;
+                            } else {
+                                sv = score[d.first + j];
+                            }
+                            if (digit_of<PASS>(key_of_score(sv), prefix, &bin)) atomicAdd(&h[bin], 1u);
                         }
                     }
                 }
@@ -228,6 +248,30 @@ __global__ __launch_bounds__(HIST_THREADS) void k_sel_hist(const float* __restri
                 if (fin.need_rank) atomicOr((int*)&ws.done[127], 1);
                 if (thr_out) thr_out[seq] = fin.thr_key;
                 ws.sel[seq] = fin;
+            }
+            // The bound the decode-step selection starts from at its next call (k_fastsel.hip): a key with about
+            // 2 (k + 1) retained entries between it and the threshold (seed_distance).  The entry of
+            // that rank is walked down the three histograms as far as it shares the threshold's digits (below that
+            // the histograms count other buckets); where it leaves them, the upper edge of its bucket is taken.
+            if (!PAGED && ws.fl_cap > 0 && st.count > st.want) {
+                SelState sb = ws.sel[(size_t)sh.n_seq + seq];     // state before the first digit
+                const int64_t above = seed_distance(st.count - st.want, sh.segs_per_seq, ws.fl_cap);
+                sb.rank = st.want - above >= 1 ? st.want - above : 1;
+                uint32_t unused;
+                uint64_t seed;
+                sb = next_digit<0>(ws.hist, sh.n_seq, seq, sb, lds64, &s_state, &unused);
+                if (sb.prefix != (fin.prefix >> 21)) {
+                    seed = ((uint64_t)sb.prefix + 1) << 21;
+                } else {
+                    sb = next_digit<1>(ws.hist + (size_t)1 * HIST_REPLICAS * sh.n_seq * RADIX_BINS, sh.n_seq, seq, sb, lds64, &s_state, &unused);
+                    if (sb.prefix != (fin.prefix >> 10)) {
+                        seed = ((uint64_t)sb.prefix + 1) << 10;
+                    } else {
+                        sb = next_digit<2>(hist_pass, sh.n_seq, seq, sb, lds64, &s_state, &unused);
+                        seed = (uint64_t)sb.prefix + 1;
+                    }
+                }
+                if (tid == 0) ws.fast_hi[seq] = seed > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)seed;
             }
         }
     }
@@ -362,18 +406,20 @@ void launch_select_passes_paged(kvtrim_ctx* ctx, const float* score, const SelTa
     const Workspace& ws = ctx->ws;
     if (pass == 0) {
         ProfScope prof(ctx, K_SEL_HIST0, st);
-        hipLaunchKernelGGL((k_sel_hist<0, 7, true>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr);
+        hipLaunchKernelGGL((k_sel_hist<0, 7, true>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr, CacheView(), nullptr, nullptr);
     } else if (pass == 1) {
         ProfScope prof(ctx, K_SEL_HIST1, st);
-        hipLaunchKernelGGL((k_sel_hist<1, 7, true>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr);
+        hipLaunchKernelGGL((k_sel_hist<1, 7, true>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr, CacheView(), nullptr, nullptr);
     } else {
         ProfScope prof(ctx, K_SEL_HIST2, st);
-        hipLaunchKernelGGL((k_sel_hist<2, 7, true>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr);
+        hipLaunchKernelGGL((k_sel_hist<2, 7, true>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr, CacheView(), nullptr, nullptr);
     }
 }
 
-kvtrim_status launch_select(kvtrim_ctx* ctx, const CacheView& c, const float* score, const int64_t* budget,
-                            uint8_t* keep, int32_t* kept, uint32_t* thr, hipStream_t st) {
+// now != NULL: stage 1 is fused into the first pass, which writes the scores to score_w.
+static kvtrim_status launch_select_impl(kvtrim_ctx* ctx, const CacheView& c, const float* score, const int32_t* now,
+                                        float* score_w, const int64_t* budget, uint8_t* keep, int32_t* kept,
+                                        uint32_t* thr, hipStream_t st) {
     const Shape& sh = ctx->shape;
     const Workspace& ws = ctx->ws;
     const int64_t max_chunks = c.cap / SEL_CHUNK + sh.nseg;      // bound on the chunk count
@@ -386,17 +432,30 @@ kvtrim_status launch_select(kvtrim_ctx* ctx, const CacheView& c, const float* sc
     { ProfScope prof(ctx, K_SEL_PLAN, st);
       hipLaunchKernelGGL(k_sel_plan, dim3(1 + PLAN_ZERO_BLOCKS), dim3(1024), 0, st, c, sh, budget, ws, kept, thr, hist_blocks); }
     { ProfScope prof(ctx, K_SEL_HIST0, st);
-      hipLaunchKernelGGL((k_sel_hist<0, SEL_SHIFT, false>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr); }
+      if (now)
+          hipLaunchKernelGGL((k_sel_hist<0, SEL_SHIFT, false, true>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, (const float*)nullptr, sh, ws, tb, thr, c, now, score_w);
+      else
+          hipLaunchKernelGGL((k_sel_hist<0, SEL_SHIFT, false>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr, c, nullptr, nullptr); }
     { ProfScope prof(ctx, K_SEL_HIST1, st);
-      hipLaunchKernelGGL((k_sel_hist<1, SEL_SHIFT, false>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr); }
+      hipLaunchKernelGGL((k_sel_hist<1, SEL_SHIFT, false>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr, c, nullptr, nullptr); }
     { ProfScope prof(ctx, K_SEL_HIST2, st);
-      hipLaunchKernelGGL((k_sel_hist<2, SEL_SHIFT, false>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr); }
+      hipLaunchKernelGGL((k_sel_hist<2, SEL_SHIFT, false>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr, c, nullptr, nullptr); }
     { ProfScope prof(ctx, K_SEL_COUNT, st);
       hipLaunchKernelGGL(k_sel_count, dim3(n_chunk_blocks < 256 ? n_chunk_blocks : 256), dim3(CNT_THREADS), 0, st, score, sh, ws, tb, kept); }
     { ProfScope prof(ctx, K_SEL_MASK, st);
       hipLaunchKernelGGL(k_sel_mask, dim3(n_chunk_blocks), dim3(SEL_THREADS), 0, st, score, sh, ws, tb, keep, kept); }
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;
+}
+
+kvtrim_status launch_select(kvtrim_ctx* ctx, const CacheView& c, const float* score, const int64_t* budget,
+                            uint8_t* keep, int32_t* kept, uint32_t* thr, hipStream_t st) {
+    return launch_select_impl(ctx, c, score, nullptr, nullptr, budget, keep, kept, thr, st);
+}
+
+kvtrim_status launch_score_select_general(kvtrim_ctx* ctx, const CacheView& c, const int32_t* now, const int64_t* budget,
+                                          float* score, uint8_t* keep, int32_t* kept, uint32_t* thr, hipStream_t st) {
+    return launch_select_impl(ctx, c, score, now, score, budget, keep, kept, thr, st);
 }
 
 }  // namespace kvtrim

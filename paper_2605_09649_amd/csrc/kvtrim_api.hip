@@ -33,7 +33,8 @@ static bool config_ok(const kvtrim_config* c) {
 }
 
 struct Layout {
-    size_t off[24];
+    size_t off[32];
+    int32_t fl_cap;
     size_t total;
     int64_t max_sel_chunks, max_cmp_chunks, max_att_chunks;
 };
@@ -74,7 +75,7 @@ static Layout layout_of(const kvtrim_config* c, bool select_only) {
     l.off[10] = bump(cur, seg_tables * (nseg + 1) * sizeof(int32_t));          // att_chunk_prefix
     l.off[11] = bump(cur, l.max_att_chunks * sizeof(ChunkDesc));               // att_desc
     l.off[12] = bump(cur, (size_t)l.max_att_chunks * G * (c->head_dim + 2) * sizeof(float)); // att_partial
-    l.off[13] = bump(cur, 256);                                                // err
+    l.off[13] = bump(cur, 256);                                                // err (word 0), fast_stat (bytes 64..79)
     l.off[14] = bump(cur, (nseg + 1) * sizeof(int64_t));                       // sel_entry_prefix
     l.off[15] = bump(cur, HIST_BLOCKS_MAX * sizeof(int4));                     // sel_blk
     l.off[16] = bump(cur, seg_tables * (size_t)nseg * sizeof(int32_t));        // tie_cnt
@@ -85,6 +86,18 @@ static Layout layout_of(const kvtrim_config* c, bool select_only) {
     l.off[21] = bump(cur, (size_t)c->n_seq * sizeof(uint32_t));                // seq_done
     l.off[22] = bump(cur, seg_tables * (size_t)nseg * sizeof(int32_t));        // chunk_old_len
     l.off[23] = bump(cur, l.max_att_chunks * sizeof(int64_t));                 // run_dst
+    // decode-step selection: a candidate list per sequence, shorter when there are many sequences (1 M entries in all)
+    int64_t fl = ((int64_t)1 << 20) / c->n_seq / 64 * 64;
+    fl = fl > FL_CAP_MAX ? FL_CAP_MAX : (fl < FL_CAP_MIN ? FL_CAP_MIN : fl);
+    l.fl_cap = select_only ? 0 : (int32_t)fl;
+    l.off[24] = bump(cur, seg_tables * (size_t)c->n_seq * sizeof(uint32_t));   // fast_hi
+    l.off[25] = bump(cur, seg_tables * (size_t)c->n_seq * 16 * sizeof(uint32_t));   // fast_min: 16 group words per sequence
+    l.off[26] = bump(cur, seg_tables * (size_t)c->n_seq * 17 * sizeof(uint32_t));   // fast_done: top-level + 16 group counters
+    l.off[27] = bump(cur, seg_tables * (size_t)c->n_seq * 16 * sizeof(uint32_t));   // fl_count: one per sub-list
+    l.off[28] = bump(cur, seg_tables * (size_t)c->n_seq * sizeof(FastSel));    // fast_sel
+    l.off[29] = bump(cur, (size_t)c->n_seq * l.fl_cap * sizeof(uint32_t));     // fl_key
+    l.off[30] = bump(cur, (size_t)c->n_seq * l.fl_cap * sizeof(int32_t));      // fl_seg
+    l.off[31] = bump(cur, (size_t)c->n_seq * l.fl_cap * sizeof(int32_t));      // fl_pos
     l.total = (cur + 255) & ~(size_t)255;
     return l;
 }
@@ -105,6 +118,7 @@ static void bind(const Layout& l, char* b, Workspace& w) {
     w.att_partial = (float*)(b + l.off[12]);
     w.pg_block_table = nullptr;
     w.err = (int32_t*)(b + l.off[13]);
+    w.fast_stat = (unsigned long long*)(b + l.off[13] + 64);
     w.sel_entry_prefix = (int64_t*)(b + l.off[14]);
     w.sel_blk = (int4*)(b + l.off[15]);
     w.tie_cnt = (int32_t*)(b + l.off[16]);
@@ -115,6 +129,15 @@ static void bind(const Layout& l, char* b, Workspace& w) {
     w.seq_done = (uint32_t*)(b + l.off[21]);
     w.chunk_old_len = (int32_t*)(b + l.off[22]);
     w.run_dst = (int64_t*)(b + l.off[23]);
+    w.fast_hi = (uint32_t*)(b + l.off[24]);
+    w.fast_min = (uint32_t*)(b + l.off[25]);
+    w.fast_done = (uint32_t*)(b + l.off[26]);
+    w.fl_count = (uint32_t*)(b + l.off[27]);
+    w.fast_sel = (FastSel*)(b + l.off[28]);
+    w.fl_key = (uint32_t*)(b + l.off[29]);
+    w.fl_seg = (int32_t*)(b + l.off[30]);
+    w.fl_pos = (int32_t*)(b + l.off[31]);
+    w.fl_cap = l.fl_cap;
     w.max_sel_chunks = l.max_sel_chunks;
     w.max_cmp_chunks = l.max_cmp_chunks;
     w.max_att_chunks = l.max_att_chunks;
@@ -207,7 +230,9 @@ kvtrim_status kvtrim_create(kvtrim_ctx** out, const kvtrim_config* cfg) {
         return KVTRIM_ENOMEM;
     }
     if (hipHostMalloc((void**)&ctx->err_host, sizeof(int32_t), hipHostMallocDefault) != hipSuccess ||
-        hipMemset(ctx->ws_base, 0, l.total) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+        hipMemset(ctx->ws_base, 0, l.total) != hipSuccess ||
+        hipMemset((char*)ctx->ws_base + l.off[25], 0xFF, (size_t)cfg->n_seq * 16 * sizeof(uint32_t)) != hipSuccess ||   // fast_min: "no key seen"
+        hipDeviceSynchronize() != hipSuccess) {
         (void)hipGetLastError();
         if (ctx->err_host) (void)hipHostFree(ctx->err_host);
         (void)hipFree(ctx->ws_base);
@@ -236,11 +261,12 @@ static const char* const kernel_names[KVTRIM_N_KERNELS] = {
     "k_score", "k_sel_plan", "k_sel_hist<0>", "k_sel_hist<1>", "k_sel_hist<2>", "k_sel_count", "k_sel_mask",
     "k_cmp_scan", "k_cmp_copy", "k_att_plan", "k_att_partial", "k_att_combine", "k_append", "k_cmp_attn", "k_occupancy",
     "k_pg_init", "k_pg_append", "k_pg_score", "k_pg_plan", "k_pg_count", "k_pg_evict", "k_pg_tidy", "k_pg_att_plan", "k_gate_hidden", "k_gate_readout",
-    "k_gate_fold", "k_gate_prefill", "k_gate_retile", "k_pg_defrag", "k_gate_dot", "k_att_fused", "k_cmp_unstage"};
+    "k_gate_fold", "k_gate_prefill", "k_gate_retile", "k_pg_defrag", "k_gate_dot", "k_att_fused", "k_cmp_unstage",
+    "k_fast_scan", "k_fast_mask", "reserved34", "reserved35", "reserved36", "reserved37", "reserved38", "reserved39"};
 
 const char* kvtrim_kernel_name(int32_t id) { return id >= 0 && id < KVTRIM_N_KERNELS ? kernel_names[id] : nullptr; }
 
-kvtrim_status kvtrim_profile_begin(kvtrim_ctx* ctx, uint32_t kernel_mask) {
+kvtrim_status kvtrim_profile_begin(kvtrim_ctx* ctx, uint64_t kernel_mask) {
     if (!ctx) return KVTRIM_EINVAL;
     if (!ctx->prof_ev) {
         ctx->prof_ev = new (std::nothrow) hipEvent_t[2 * KVTRIM_PROFILE_MAX_LAUNCHES]();
@@ -324,6 +350,28 @@ kvtrim_status kvtrim_select_global(kvtrim_ctx* ctx, const kvtrim_cache* c, const
     if (const char* p = cache_problem(ctx, c, false)) return invalid(ctx, p);
     if (!score || !budget || !keep_out || !kept_out) return invalid(ctx, "score / budget / keep_out / kept_out is NULL");
     return launch_select(ctx, view_of(c), score, budget, keep_out, kept_out, thr_key_out, (hipStream_t)hip_stream);
+}
+
+kvtrim_status kvtrim_select_path_counts(kvtrim_ctx* ctx, int64_t* from_list_host, int64_t* fallback_host, void* hip_stream) {
+    if (!ctx || !from_list_host || !fallback_host) return KVTRIM_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    unsigned long long v[2] = {0, 0};
+    KVTRIM_HIP(ctx, hipStreamSynchronize(st));
+    KVTRIM_HIP(ctx, hipMemcpy(v, ctx->ws.fast_stat, sizeof(v), hipMemcpyDeviceToHost));
+    *from_list_host = (int64_t)v[0];
+    *fallback_host = (int64_t)v[1];
+    return KVTRIM_OK;
+}
+
+kvtrim_status kvtrim_score_select(kvtrim_ctx* ctx, const kvtrim_cache* c, const int32_t* now, const int64_t* budget,
+                                  float* score_out, uint8_t* keep_out, int32_t* kept_out, uint32_t* thr_key_out,
+                                  int64_t evict_hint, void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    if (const char* p = cache_problem(ctx, c, false)) return invalid(ctx, p);
+    if (!now || !budget || !score_out || !keep_out || !kept_out)
+        return invalid(ctx, "now / budget / score_out / keep_out / kept_out is NULL");
+    return launch_score_select(ctx, view_of(c), now, budget, score_out, keep_out, kept_out, thr_key_out,
+                               evict_hint, (hipStream_t)hip_stream);
 }
 
 kvtrim_status kvtrim_compact(kvtrim_ctx* ctx, const kvtrim_cache* src, const uint8_t* keep, const int32_t* kept,
@@ -484,9 +532,7 @@ kvtrim_status kvtrim_append_compact(kvtrim_ctx* ctx, kvtrim_cache* src, const vo
                                      log_tail_new, pos_new, n_new, false, ctx->ws.chunk_old_len, st);
     if (rc != KVTRIM_OK) return rc;
     const CacheView sv = view_of(src);
-    rc = launch_score(ctx, sv, now, score_out, st);
-    if (rc != KVTRIM_OK) return rc;
-    rc = launch_select(ctx, sv, score_out, budget, keep_out, kept_out, thr_key_out, st);
+    rc = launch_score_select_general(ctx, sv, now, budget, score_out, keep_out, kept_out, thr_key_out, st);
     if (rc != KVTRIM_OK) return rc;
     launch_cmp_scan(ctx, sv, keep_out, kept_out, view_mut_of(dst), reserve, st);
     return launch_cmp_copy_new(ctx, sv, keep_out, view_mut_of(dst), (const uint16_t*)k_new, (const uint16_t*)v_new, n_new,

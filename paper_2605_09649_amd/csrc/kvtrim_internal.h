@@ -23,6 +23,12 @@ constexpr int HIST_BLOCKS_MAX = 256; // blocks of a histogram pass (few and fat:
 constexpr int DONE_WORDS = 128;      // 4 sets of 32 counters (three histogram passes, the tie count)
 constexpr int HIST_REPLICAS = 8;     // copies of the merged histogram (spreads the device-scope atomics)
 
+// Decode-step selection (k_fastsel.hip): candidates below the carried bound are listed per sequence.
+constexpr int FL_CAP_MAX = 4096;     // list entries per sequence (fewer when the context has many sequences)
+constexpr int FL_CAP_MIN = 64;
+constexpr int FAST_THREADS = 1024;
+constexpr int FAST_ENTRIES_PER_BLOCK = 8192;   // entries of a segment one block covers (blocks per segment from the capacity)
+
 constexpr int ERR_CAP = 1;           // bits of the sticky device flag
 constexpr int ERR_MISMATCH = 2;
 constexpr int ERR_LAYOUT = 4;
@@ -64,6 +70,17 @@ struct SelState {
     int64_t tie_quota;   // entries equal to thr_key to keep (in storage order)
     int32_t keep_none;   // want == 0
     int32_t need_rank;   // only some of the entries equal to thr_key fit: they must be ranked in order
+};
+
+// Outcome of a selection in the form the decode-step mask kernel reads: entry e of segment g survives iff
+// key(e) > key_thr, or key(e) == key_thr and (g, pos(e)) <= (seg_thr, pos_thr) lexicographically - i.e. iff it is
+// not behind the last retained entry in the total order (key descending, segment ascending, position ascending).
+constexpr int FSEL_NONE = 0, FSEL_ALL = 1, FSEL_THRESHOLD = 2;
+struct FastSel {
+    int32_t mode;
+    uint32_t key_thr;
+    int32_t seg_thr;
+    int32_t pos_thr;
 };
 
 // One chunk of a segment: entries [first, first + n) of the flat arrays.
@@ -111,6 +128,17 @@ struct Workspace {
     float* att_partial;          // [max_att_chunks][G][D+2]  (m, l, o[D]) per query head
     const int32_t* pg_block_table; // paged attention only: the caller's block tables (set per launch)
     int32_t* err;                // sticky device flag
+    // decode-step selection: state carried from call to call, and the per-call candidate lists
+    uint32_t* fast_hi;           // [n_seq] entries with key < fast_hi are listed (0: nothing known yet)
+    uint32_t* fast_min;          // [n_seq][16] smallest key seen in the call, per group of blocks (0xFFFFFFFF between calls)
+    uint32_t* fast_done;         // [n_seq][17] arrivals: top level, 16 groups of blocks (0 between calls)
+    uint32_t* fl_count;          // [n_seq][16] candidates per sub-list (beyond its capacity: the list is incomplete; 0 between calls)
+    unsigned long long* fast_stat; // [2] sequences resolved from their list / by the single-block select, since the context was created
+    FastSel* fast_sel;           // [n_seq] outcome of the call
+    uint32_t* fl_key;            // [n_seq][fl_cap] in up to 16 sub-lists of fl_cap / n_sub entries
+    int32_t* fl_seg;             // [n_seq][fl_cap]
+    int32_t* fl_pos;             // [n_seq][fl_cap]
+    int32_t fl_cap;
     int64_t max_sel_chunks, max_cmp_chunks, max_att_chunks;
 };
 
@@ -120,7 +148,8 @@ namespace kvtrim {
 enum KernelId {
     K_SCORE = 0, K_SEL_PLAN, K_SEL_HIST0, K_SEL_HIST1, K_SEL_HIST2, K_SEL_COUNT, K_SEL_MASK,
     K_CMP_SCAN, K_CMP_COPY, K_ATT_PLAN, K_ATT_PARTIAL, K_ATT_COMBINE, K_APPEND, K_CMP_ATTN, K_OCCUPANCY,
-    K_PG_INIT, K_PG_APPEND, K_PG_SCORE, K_PG_PLAN, K_PG_COUNT, K_PG_EVICT, K_PG_TIDY, K_PG_ATT_PLAN, K_GATE_HIDDEN, K_GATE_READOUT, K_GATE_FOLD, K_GATE_PREFILL, K_GATE_RETILE, K_PG_DEFRAG, K_GATE_DOT, K_ATT_FUSED, K_CMP_UNSTAGE, K_COUNT
+    K_PG_INIT, K_PG_APPEND, K_PG_SCORE, K_PG_PLAN, K_PG_COUNT, K_PG_EVICT, K_PG_TIDY, K_PG_ATT_PLAN, K_GATE_HIDDEN, K_GATE_READOUT, K_GATE_FOLD, K_GATE_PREFILL, K_GATE_RETILE, K_PG_DEFRAG, K_GATE_DOT, K_ATT_FUSED, K_CMP_UNSTAGE,
+    K_FAST_SCAN, K_FAST_MASK, K_RESERVED_34, K_RESERVED_35, K_RESERVED_36, K_RESERVED_37, K_RESERVED_38, K_RESERVED_39, K_COUNT
 };
 static_assert(K_COUNT == KVTRIM_N_KERNELS, "kernel table out of step with the header");
 }  // namespace kvtrim
@@ -136,7 +165,7 @@ struct kvtrim_ctx {
     int att_chunk_min;           // rows per attention chunk (multiple of 64, >= 256); KVTRIM_ATT_CHUNK overrides
     char last_error[256];
     // instrumentation
-    uint32_t prof_mask;
+    uint64_t prof_mask;
     hipEvent_t* prof_ev;         // [2 * KVTRIM_PROFILE_MAX_LAUNCHES] start/stop pairs
     int8_t* prof_kernel;         // kernel id of each bracketed launch
     int prof_used;
@@ -150,6 +179,13 @@ int att_chunk_for(const kvtrim_ctx* ctx, int64_t cap);
 kvtrim_status launch_score(kvtrim_ctx*, const CacheView&, const int32_t* now, float* score, hipStream_t);
 kvtrim_status launch_select(kvtrim_ctx*, const CacheView&, const float* score, const int64_t* budget,
                             uint8_t* keep, int32_t* kept, uint32_t* thr, hipStream_t);
+// Stages 1 + 2 in one call.  General form: the radix passes, the first of which computes the score on the fly and
+// writes it out.  Decode-step form (evict_hint small): one pass that scores and lists the candidates below the
+// carried bound, resolved by the last block of every sequence, and the mask pass.
+kvtrim_status launch_score_select(kvtrim_ctx*, const CacheView&, const int32_t* now, const int64_t* budget, float* score,
+                                  uint8_t* keep, int32_t* kept, uint32_t* thr, int64_t evict_hint, hipStream_t);
+kvtrim_status launch_score_select_general(kvtrim_ctx*, const CacheView&, const int32_t* now, const int64_t* budget,
+                                          float* score, uint8_t* keep, int32_t* kept, uint32_t* thr, hipStream_t);
 kvtrim_status launch_compact(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const int32_t* kept,
                              const CacheViewMut& dst, int32_t reserve, hipStream_t);
 kvtrim_status launch_attn(kvtrim_ctx*, const CacheView&, const uint16_t* q, const int32_t* soft_now,
@@ -257,6 +293,17 @@ __device__ __forceinline__ uint32_t key_of_score(float s) {
 }
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+// How many retained entries the bound of the decode-step selection is placed above the threshold when a full
+// select seeds it: twice the evictions of the call that seeds it, but at least twice a one-token decode step's
+// (one entry per segment) and at most a quarter of the candidate list - a first eviction after a prefill evicts
+// millions, the decode steps that follow it a few hundred.
+__device__ __forceinline__ int64_t seed_distance(int64_t evicted, int segs_per_seq, int fl_cap) {
+    int64_t d = 2 * (evicted + 1);
+    const int64_t lo = 2 * ((int64_t)segs_per_seq + 1), hi = fl_cap / 4;
+    d = d < lo ? lo : d;
+    return d > hi ? (hi > 1 ? hi : 1) : d;
+}
 
 // number of set bits of `mask` below this lane
 __device__ __forceinline__ int mbcnt(uint64_t mask) {

@@ -44,8 +44,9 @@ def attn_error(out_gpu, out_ref):
 class GpuLoop:
     """Device-side state of the decode loop: ping-pong caches and the per-step scratch outputs."""
 
-    def __init__(self, w, cache_dict, budget, reserve, extra_entries, device, fused=False):
-        self.w, self.device, self.reserve, self.fused = w, device, reserve, fused
+    def __init__(self, w, cache_dict, budget, reserve, extra_entries, device, fused=False, hint=None):
+        self.w, self.device, self.reserve, self.fused, self.hint = w, device, reserve, fused, hint
+        self.calls = 0
         self.src = kv.Cache.from_dict(cache_dict, device)
         total = int(cache_dict["seg_len"].sum())
         dst_cap = min(int(sum(budget)), total + extra_entries) + w.nseg * reserve + 8
@@ -68,8 +69,14 @@ class GpuLoop:
         ctx = self.ctx
         kv.kvtrim_append(ctx, self.src, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos_new_dev, 1,
                          log_tail_new=inp.get("log_tail_new"))
-        kv.kvtrim_score(ctx, self.src, now_dev, self.score)
-        kv.kvtrim_select_global(ctx, self.src, self.score, self.budget, self.keep, self.kept, self.thr)
+        if self.hint is None:
+            kv.kvtrim_score(ctx, self.src, now_dev, self.score)
+            kv.kvtrim_select_global(ctx, self.src, self.score, self.budget, self.keep, self.kept, self.thr)
+        else:                                      # stages 1 + 2 in one call (hint 0: radix passes; > 0: decode-step form)
+            hint = self.hint[min(self.calls, len(self.hint) - 1)] if isinstance(self.hint, (list, tuple)) else self.hint
+            self.calls += 1
+            kv.kvtrim_score_select(ctx, self.src, now_dev, self.budget, self.score, self.keep, self.kept, self.thr,
+                                   evict_hint=hint)
         dst = self.spare[self.flip]
         if self.fused:
             kv.kvtrim_compact_attn(ctx, self.src, self.keep, self.kept, dst, self.reserve, inp["q"], 0,
@@ -86,19 +93,24 @@ class GpuLoop:
         self.flip ^= 1
 
 
-def run_steps_both(w, steps, budget, device="cuda:0", reserve=1, cache_dict=None, now0=None, fused=False, horizon=1):
-    """Returns one dict per step with the comparison results."""
+def run_steps_both(w, steps, budget, device="cuda:0", reserve=1, cache_dict=None, now0=None, fused=False, horizon=1,
+                   hint=None, budget_per_step=None):
+    """Returns one dict per step with the comparison results.  hint: None = kvtrim_score + kvtrim_select_global,
+    otherwise kvtrim_score_select with that evict_hint.  budget_per_step: a list of budgets, one per step."""
     if cache_dict is None:
         cache_dict = ki.prefill_cache(w, reserve=reserve)
         now0 = [t - 1 for t in w.prefill]
     cache_dict = ki.with_horizon(cache_dict, horizon)
     hc = host_cache(w, cache_dict)
-    gpu = GpuLoop(w, cache_dict, budget, reserve, steps * w.nseg, device, fused=fused)
+    gpu = GpuLoop(w, cache_dict, budget, reserve, steps * w.nseg, device, fused=fused, hint=hint)
     budget_np = np.array(list(budget), np.int64)
     now = np.array(now0, np.int32)
     per_seq = w.n_layers * w.n_kv_heads
     results = []
     for step in range(steps):
+        if budget_per_step is not None:
+            budget_np = np.array(list(budget_per_step[step]), np.int64)
+            gpu.budget.copy_(torch.from_numpy(budget_np))
         inp = ki.decode_inputs(w, step, horizon=horizon)
         now = now + 1
         pos_new = np.repeat(now, per_seq).astype(np.int32)
@@ -128,6 +140,8 @@ def run_steps_both(w, steps, budget, device="cuda:0", reserve=1, cache_dict=None
             "attn_err": attn_error(gpu.out.cpu().numpy(), out_ref),
             "kept_total": int(kept_ref.sum()),
         }
+        if hint is not None:
+            res["path_counts"] = kv.kvtrim_select_path_counts(gpu.ctx)
         fin = np.isfinite(lse_ref)
         lse_gpu = gpu.lse.cpu().numpy()
         res["lse_err"] = float(np.abs(lse_gpu[fin] - lse_ref[fin]).max()) if fin.any() else 0.0
