@@ -13,6 +13,7 @@
 namespace kvtrim {
 
 constexpr int SCAN_THREADS = 1024;
+constexpr int SCAN_BATCH = 8;          // chunks whose mask bytes a wavefront requests before it counts any
 
 // Sums N values over the block with one pair of barriers; every thread gets every sum.
 template <int N>
@@ -101,33 +102,76 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const 
                                                            int run) {
     __shared__ int64_t lds64[17];
     __shared__ int64_t lds_n[16 * 8];
+    __shared__ int s_cnt[SCAN_THREADS];
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int g = blockIdx.x;
     const int nseg = sh.nseg;
 
+    // Order of the memory traffic: (1) this segment's own table entry; (2) in one round, the table entries of all
+    // segments (for the prefixes; !PRE) and the mask bytes of this segment's first SCAN_THREADS chunks; then
+    // arithmetic only; (3) the stores.  A decode-step segment is done after two dependent round trips.
+    const int len_raw = src.seg_len[g];
+    const int64_t start = src.seg_start[g];
+    const bool own_ok = len_raw >= 0 && start >= 0 && start + len_raw <= src.cap;   // (checked for all segments below / by k_cmp_prefix)
+    const int len = own_ok ? len_raw : 0;
+    const int nch = len > 0 ? (len + CMP_CHUNK - 1) / CMP_CHUNK : 0;
+    const uint8_t* kp = keep + start;
+
     int64_t chunks_before, dst_before, runs_before = 0;
+    int o_len = 0, o_kp = 0;                                      // !PRE: table entry of segment `tid`
+    int64_t o_st = 0;
     if (PRE) {
         if (__hip_atomic_load(ws.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
         chunks_before = ws.cmp_chunk_prefix[g];
         dst_before = dst.seg_start[g];
         if (run > 0) runs_before = ws.att_chunk_prefix[g];
-    } else {
+    } else if (tid < nseg) {                                      // (nseg <= SCAN_THREADS without k_cmp_prefix)
+        o_len = src.seg_len[tid];
+        o_st = src.seg_start[tid];
+        o_kp = kept[tid];
+    }
+
+    // survivors per chunk of one tile of SCAN_THREADS chunks into s_cnt: one wavefront per chunk, two coalesced byte
+    // loads per lane; a wavefront requests the bytes of up to SCAN_BATCH of its chunks before it counts any
+    uint8_t b[SCAN_BATCH][CMP_CHUNK / 64];
+    auto request = [&](int tile0, int tile_n, int c0) {
+#pragma unroll
+        for (int u = 0; u < SCAN_BATCH; ++u) {
+            const int ch = tile0 + c0 + u * (SCAN_THREADS / 64);
+#pragma unroll
+            for (int r = 0; r < CMP_CHUNK / 64; ++r) {
+                const int64_t j = (int64_t)ch * CMP_CHUNK + r * 64 + lane;
+                b[u][r] = (c0 + u * (SCAN_THREADS / 64) < tile_n && j < len) ? kp[j] : (uint8_t)0;
+            }
+        }
+    };
+    auto count = [&](int tile_n, int c0) {
+#pragma unroll
+        for (int u = 0; u < SCAN_BATCH; ++u) {
+            int cnt = 0;
+#pragma unroll
+            for (int r = 0; r < CMP_CHUNK / 64; ++r) cnt += __popcll(__ballot(b[u][r] != 0));
+            const int cl = c0 + u * (SCAN_THREADS / 64);
+            if (lane == 0 && cl < tile_n) s_cnt[cl] = cnt;
+        }
+    };
+    request(0, min(SCAN_THREADS, nch), wave);                     // in flight while the prefixes are summed
+
+    if (!PRE) {
         // chunks and destination entries of the segments before g, and the totals
         int64_t acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // chunks_before, dst_before, dst_total, chunks_total, bad_layout, bad_kept, runs_before, runs_total
-        for (int i = tid; i < nseg; i += SCAN_THREADS) {
-            const int len = src.seg_len[i];
-            const int64_t st = src.seg_start[i];
-            const int kp = kept[i];
-            acc[4] |= (len < 0 || st < 0 || st + len > src.cap);
-            acc[5] |= (kp < 0 || kp > len);
-            const int64_t nch = len > 0 ? ((int64_t)len + CMP_CHUNK - 1) / CMP_CHUNK : 0;
-            const int64_t need = ((int64_t)kp + reserve + align - 1) / align * align;   // align = 1 unless pages are built
-            const int64_t nrun = run > 0 && len > 0 ? ((int64_t)len + run - 1) / run : 0;
-            acc[3] += nch;
+        if (tid < nseg) {
+            const int i = tid;
+            acc[4] |= (o_len < 0 || o_st < 0 || o_st + o_len > src.cap);
+            acc[5] |= (o_kp < 0 || o_kp > o_len);
+            const int64_t nc = o_len > 0 ? ((int64_t)o_len + CMP_CHUNK - 1) / CMP_CHUNK : 0;
+            const int64_t need = ((int64_t)o_kp + reserve + align - 1) / align * align;   // align = 1 unless pages are built
+            const int64_t nrun = run > 0 && o_len > 0 ? ((int64_t)o_len + run - 1) / run : 0;
+            acc[3] += nc;
             acc[2] += need;
             acc[7] += nrun;
             if (i < g) {
-                acc[0] += nch;
+                acc[0] += nc;
                 acc[1] += need;
                 acc[6] += nrun;
             }
@@ -138,7 +182,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const 
         runs_before = acc[6];
         const int64_t dst_total = acc[2], chunks_total = acc[3];
         const bool bad_layout = acc[4] != 0 || chunks_total > ws.max_cmp_chunks || acc[7] > ws.max_att_chunks, bad_kept = acc[5] != 0;
-        if (inplace) dst_before = src.seg_start[g];               // the segment keeps its place
+        if (inplace) dst_before = start;                          // the segment keeps its place
         if (bad_layout || bad_kept || (!inplace && dst_total > dst.cap)) {   // every block takes the same decision
             if (tid == 0) {
                 atomicOr(ws.err, bad_layout ? ERR_LAYOUT : (bad_kept ? ERR_MISMATCH : ERR_CAP));
@@ -151,10 +195,6 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const 
         }
     }
 
-    const int len = src.seg_len[g];
-    const int64_t start = src.seg_start[g];
-    const int nch = len > 0 ? (len + CMP_CHUNK - 1) / CMP_CHUNK : 0;
-    const uint8_t* kp = keep + start;
     const int cbase = (int)chunks_before;
     if (run > 0) {                                                // the segment's runs, for the loop-shaped fused kernel
         const int nrun = len > 0 ? (int)(((int64_t)len + run - 1) / run) : 0;
@@ -171,35 +211,31 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const 
         }
     }
 
-    // phase 1: survivors per chunk (one wavefront per chunk, two coalesced byte loads per lane)
-    for (int ch = wave; ch < nch; ch += SCAN_THREADS / 64) {
-        int cnt = 0;
-#pragma unroll
-        for (int r = 0; r < CMP_CHUNK / 64; ++r) {
-            const int j = ch * CMP_CHUNK + r * 64 + lane;
-            const bool f = j < len && kp[j] != 0;
-            cnt += __popcll(__ballot(f));
+    // Tiles of SCAN_THREADS chunks: counts (phase 1, above), then a thread per chunk - exclusive scan of the counts,
+    // destination offset and descriptor of every chunk (phase 2).
+    int64_t running = 0;
+    for (int tile0 = 0; tile0 < nch; tile0 += SCAN_THREADS) {
+        const int tile_n = min(SCAN_THREADS, nch - tile0);
+        __syncthreads();                                          // s_cnt of the previous tile has been read
+        for (int c0 = wave; c0 < tile_n; c0 += (SCAN_THREADS / 64) * SCAN_BATCH) {
+            if (tile0 > 0 || c0 > wave) request(tile0, tile_n, c0);   // (the first batch of the first tile is already here)
+            count(tile_n, c0);
         }
-        if (lane == 0) {
-            ws.cmp_chunk_dst[cbase + ch] = cnt;
+        __syncthreads();
+        const int ch = tile0 + tid;
+        const int64_t v = tid < tile_n ? s_cnt[tid] : 0;
+        int64_t tot;
+        const int64_t ex = block_excl_scan<int64_t>(v, lds64, &tot);
+        if (tid < tile_n) {
+            const int n = min(CMP_CHUNK, len - ch * CMP_CHUNK);
+            // a chunk that loses nothing is marked: its mover needs neither the mask nor the ranks
+            ws.cmp_chunk_dst[cbase + ch] = (dst_before + running + ex) | (v == n ? CMP_DST_FULL : 0);
             ChunkDesc d;
             d.first = start + (int64_t)ch * CMP_CHUNK;
-            d.n = min(CMP_CHUNK, len - ch * CMP_CHUNK);
+            d.n = n;
             d.seg = g;
             ws.cmp_desc[cbase + ch] = d;
         }
-    }
-    __syncthreads();
-    // phase 2: exclusive scan of the counts inside the segment
-    int64_t running = 0;
-    for (int base = 0; base < nch; base += SCAN_THREADS) {
-        const int ch = base + tid;
-        const int64_t v = ch < nch ? ws.cmp_chunk_dst[cbase + ch] : 0;
-        int64_t tot;
-        const int64_t ex = block_excl_scan<int64_t>(v, lds64, &tot);
-        // a chunk that loses nothing is marked: its mover needs neither the mask nor the ranks
-        if (ch < nch)
-            ws.cmp_chunk_dst[cbase + ch] = (dst_before + running + ex) | (v == min(CMP_CHUNK, len - ch * CMP_CHUNK) ? CMP_DST_FULL : 0);
         running += tot;
     }
     if (run > 0) {
