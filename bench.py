@@ -21,11 +21,37 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 CPU_STEPS = 16                 # steps the CPU oracle replays after the timed region (a few seconds of host work)
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE runs, scaled by a plain copy kernel; None until measured for this workload.
-MEASURED_TRAFFIC = {("long", "k_cmp_attn"): 1.1011e9 + 1.1259e9, ("long", "k_cmp_copy"): None,
-                    ("long-paged", "k_att_partial"): 1.0942e9 + 8.8e6, ("gate-1", "k_gate_hidden"): 136.5e6 + 65.5e3,
-                    ("long-inplace", "k_cmp_attn"): 1.1012e9 + 0.2459e9}
+CPU_STEPS_ONE_THREAD = 2       # of these, with the oracle's threaded stage held to one thread
+WHOLE_CACHE_PARITY_BYTES = 6e9 # live K/V above this: the oracle checks selection and metadata whole, rows and attention on sampled segments
+
+
+def kernel_sources_sha16():
+    """Hash of the kernel sources: a traffic figure from rocprofv3 counters is quoted only while it is unchanged."""
+    import hashlib
+    d = os.path.join(ROOT, "paper_2605_09649_amd", "csrc")
+    h = hashlib.sha256()
+    for f in sorted(os.listdir(d)):
+        if f.endswith((".hip", ".h")):
+            h.update(f.encode())
+            h.update(open(os.path.join(d, f), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(tag, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of workload/variant `tag`
+    (profiles/<tag>_hbm_traffic_pmc.txt: FETCH_SIZE and WRITE_SIZE, each scaled by what the counter reads for a plain
+    copy of known size), or None when there is no such summary or the kernels have changed since it was taken."""
+    path = os.path.join(ROOT, "profiles", f"{tag}_hbm_traffic_pmc.txt")
+    if not os.path.exists(path):
+        return None
+    sha, val = None, None
+    for line in open(path):
+        p = line.split()
+        if len(p) >= 3 and p[0] == "#" and p[1] == "kernel_sources_sha16":
+            sha = p[2]
+        if len(p) >= 4 and p[0] == "#" and p[1] == "traffic_bytes_per_launch" and p[2] == kernel:
+            val = float(p[3])
+    return val if sha == kernel_sources_sha16() else None
 
 
 def rows_moved_in_place(cache, keep):
@@ -129,7 +155,7 @@ def bench_gate(args):
         alg_hidden = w1_bytes + L * n_tok * dm * 2 + L * n_tok * dg * 4
         if n_tok <= 64:
             roof = {"bound": "hbm", "kernel": first, "achieved": alg_hidden / (h_ms * 1e-3) / 1e9,
-                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": MEASURED_TRAFFIC.get((f"gate-{n_tok}", first)),
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": measured_traffic(f"gate_decode_{n_tok}tok", first),
                     "algorithmic_bytes_per_launch": alg_hidden}
         else:
             roof = {"bound": "mfma", "kernel": first, "achieved": flops_hidden / (h_ms * 1e-3) / 1e12,
@@ -290,6 +316,553 @@ def bench_chunk(args):
     }), flush=True)
 
 
+METRIC_LONG = "eviction+decode steps/sec and achieved HBM GB/s (% of peak), 32Lx8H 128K ctx"
+
+
+def metric_name(w):
+    if w.name == "long" and w.prefill[0] == 131072:
+        return METRIC_LONG
+    return (f"eviction+decode steps/sec and achieved HBM GB/s (% of peak), {w.n_seq} x {w.n_layers}Lx{w.n_kv_heads}H, "
+            f"{max(w.prefill)} ctx ({w.name})")
+
+
+class Runner:
+    """Device-side state of the decode loop of one workload in one variant (ragged out of place / in place / two
+    calls / paged), with all step inputs resident in HBM, and one step of it through the C ABI."""
+
+    def __init__(self, w, args, n_steps, reserve, dev="cuda:0"):
+        import numpy as np
+        import torch
+        import kvtrim_inputs as ki
+        import paper_2605_09649_amd as kv
+        self.w, self.args, self.kv, self.reserve, self.dev = w, args, kv, reserve, dev
+        self.per_seq = w.n_layers * w.n_kv_heads
+        pre = ki.with_horizon(ki.prefill_cache(w, reserve=reserve, device=dev), args.horizon)
+        self.total0 = sum(w.prefill) * self.per_seq
+        B = sum(w.budget)
+        tail = args.horizon != 1
+        dst_cap = min(B, self.total0 + n_steps * w.nseg) + w.nseg * reserve + 8
+        self.src = kv.Cache.from_dict(pre, dev)
+        del pre
+        self.spare, self.pc = [], None
+        if args.paged:
+            # room for the budget, one partly filled page per segment, and the pages that segments take while
+            # their own still hold scattered free slots elsewhere
+            n_pages = (min(B, self.total0 + n_steps * w.nseg) + kv.PAGE_SIZE - 1) // kv.PAGE_SIZE + 3 * w.nseg + 64
+            self.pc = kv.PagedCache(w.nseg, w.head_dim, n_pages, n_pages, dev, with_tail=tail)
+            dst_cap = n_pages * kv.PAGE_SIZE
+        else:
+            self.spare = [kv.Cache.empty(w.nseg, w.head_dim, dst_cap, dev, with_tail=tail) for _ in range(2)]
+        self.dst_cap = dst_cap
+        self.cap = cap = max(self.src.cap, dst_cap)
+        self.ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, cap)
+        self.score = torch.zeros(cap, dtype=torch.float32, device=dev)
+        self.keep = torch.zeros(cap, dtype=torch.uint8, device=dev)
+        self.kept = torch.zeros(w.nseg, dtype=torch.int32, device=dev)
+        self.thr = torch.zeros(w.n_seq, dtype=torch.int32, device=dev)
+        self.budget = torch.tensor(list(w.budget), dtype=torch.int64, device=dev)
+        self.out = torch.zeros(w.n_seq, w.n_layers, w.n_q_heads, w.head_dim, dtype=torch.float32, device=dev)
+        self.lse = torch.zeros(w.n_seq, w.n_layers, w.n_q_heads, dtype=torch.float32, device=dev)
+        self.scale = 1.0 / math.sqrt(w.head_dim)
+        # every step's inputs are generated before the timed region and stay resident in HBM
+        self.inputs, self.nows, self.pos_news = [], [], []
+        self.now0 = np.array([t - 1 for t in w.prefill], np.int32)
+        for s in range(n_steps):
+            self.inputs.append(ki.decode_inputs(w, s, device=dev, horizon=args.horizon))
+            now = self.now0 + s + 1
+            self.nows.append(torch.from_numpy(now).to(dev))
+            self.pos_news.append(torch.from_numpy(np.repeat(now, self.per_seq).astype(np.int32)).to(dev))
+        self.cur, self.flip = self.src, 0
+        torch.cuda.synchronize()
+
+    def select(self, s, cur):
+        kv, a = self.kv, self.args
+        if a.separate_score_select:
+            kv.kvtrim_score(self.ctx, cur, self.nows[s], self.score)
+            kv.kvtrim_select_global(self.ctx, cur, self.score, self.budget, self.keep, self.kept, self.thr)
+        else:
+            # first step: eviction from the whole prefill (hint 0: the radix passes); decode steps: one entry per
+            # segment comes in, so about as many go
+            kv.kvtrim_score_select(self.ctx, cur, self.nows[s], self.budget, self.score, self.keep, self.kept, self.thr,
+                                   evict_hint=self.per_seq if s > 0 else 0)
+
+    def step(self, s):
+        kv, a, w, ctx = self.kv, self.args, self.w, self.ctx
+        inp = self.inputs[s]
+        out, lse, scale = self.out, self.lse, self.scale
+        if a.paged and s > 0:
+            pc = self.pc
+            kv.kvtrim_paged_append(ctx, pc, inp["k_new"], inp["v_new"], inp["log_beta_new"], self.pos_news[s],
+                                   log_tail_new=inp.get("log_tail_new"))
+            kv.kvtrim_paged_score(ctx, pc, self.nows[s], self.score)
+            kv.kvtrim_paged_select(ctx, pc, self.score, self.budget, self.keep, self.kept, self.thr)
+            kv.kvtrim_paged_evict(ctx, pc, self.keep)
+            if a.defrag_every and s % a.defrag_every == 0:
+                kv.kvtrim_paged_defrag(ctx, pc)
+            kv.kvtrim_paged_attn(ctx, pc, inp["q"], 0, w.n_layers, scale, out, lse)
+            return
+        cur = self.cur
+        kv.kvtrim_append(ctx, cur, inp["k_new"], inp["v_new"], inp["log_beta_new"], self.pos_news[s], 1,
+                         log_tail_new=inp.get("log_tail_new"))
+        self.select(s, cur)
+        if a.paged:                             # first step: the survivors of the prefill go into pages
+            kv.kvtrim_paged_build(ctx, cur, self.keep, self.kept, self.pc)
+            kv.kvtrim_paged_attn(ctx, self.pc, inp["q"], 0, w.n_layers, scale, out, lse)
+            self.cur = self.src = None
+            return
+        dst = self.spare[self.flip]
+        if a.inplace and s > 0 and s % a.inplace:
+            # the other cache lends its arrays as parking space; the segments stay where they are
+            if a.unfused:                      # stage 3 alone in place, then the stand-alone attention on the same cache
+                kv.kvtrim_compact_inplace(ctx, cur, self.keep, self.kept, dst)
+                kv.kvtrim_decode_attn(ctx, cur, inp["q"], 0, w.n_layers, scale, out, lse)
+            else:
+                kv.kvtrim_compact_attn_inplace(ctx, cur, self.keep, self.kept, dst, inp["q"], 0, w.n_layers, scale, out, lse)
+            return
+        if a.unfused:
+            kv.kvtrim_compact(ctx, cur, self.keep, self.kept, dst, self.reserve)
+            kv.kvtrim_decode_attn(ctx, dst, inp["q"], 0, w.n_layers, scale, out, lse)
+        else:
+            kv.kvtrim_compact_attn(ctx, cur, self.keep, self.kept, dst, self.reserve, inp["q"], 0, w.n_layers, scale, out, lse)
+        self.cur = dst
+        self.src = None                         # (drops the prefill cache after the first step)
+        self.flip ^= 1
+
+
+def moved_bytes(w, a, n_cand, n_ret, rows_written_in_place=None):
+    """Compulsory HBM bytes of the calls a step actually makes (every array counted once per kernel that has to
+    read or write it) - unlike the stage-by-stage model, which charges the attention a second read of K/V that the
+    fused call does not make."""
+    D = w.head_dim
+    tail = 0 if a.horizon == 1 else 4
+    R = 4 * D + 8 + tail
+    nq = w.n_seq * w.n_layers * w.n_q_heads
+    m = {"append": 2 * R * w.nseg}
+    if a.separate_score_select or a.paged:
+        m["score"] = (8 + tail + 4) * n_cand                       # log beta, position (, tail) in; score out
+        m["select"] = (3 * 4 + 4 + 1) * n_cand                     # three histogram passes and the mask pass read the score; mask out
+    else:
+        m["score_select"] = (8 + tail + 4 + 4 + 1) * n_cand        # one scoring pass (score out), one mask pass (score in, mask out)
+    if a.paged:
+        m["evict"] = 5 * n_cand                                    # mask and position in (the few freed slots out)
+        m["attend"] = (4 * D + 4) * n_ret + 6 * D * nq             # K, V and position of every live slot; q in, out out
+    elif a.inplace:
+        per_ip = n_cand + R * n_ret + R * (rows_written_in_place or 0) + 6 * D * nq
+        per_oop = n_cand + 2 * R * n_ret + 6 * D * nq
+        m["compact_attn (in place; one step in %d out of place)" % a.inplace] = ((a.inplace - 1) * per_ip + per_oop) // a.inplace
+        if a.unfused:
+            m["decode_attn"] = 4 * D * n_ret + 6 * D * nq
+    elif a.unfused:
+        m["compact"] = n_cand + 2 * R * n_ret
+        m["decode_attn"] = 4 * D * n_ret + 6 * D * nq
+    else:
+        m["compact_attn"] = n_cand + 2 * R * n_ret + 6 * D * nq    # mask in; every retained entry in and out once; q in, out out
+    return m
+
+
+def run_decode(args, brief=False):
+    """Decode steps of one workload in one variant; returns the result (what a stand-alone run prints as its JSON line).
+    brief: a side measurement of the default run - no in-place leg and no extra runs behind it."""
+    import gc
+    import numpy as np
+    import torch
+    import kvtrim_inputs as ki
+    import paper_2605_09649_amd as kv
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = ki.workload(args.workload, prefill=args.prefill)
+    reserve = args.inplace if args.inplace else 1                 # free slots behind every segment after an out-of-place step
+    K, W = args.steps, max(args.warmup, 1)
+    cpu_steps = 0 if args.no_cpu_baseline else args.cpu_steps
+    cpu_steps_1t = min(CPU_STEPS_ONE_THREAD, cpu_steps // 2)
+    G_STEPS = 20 if args.graph else 0         # eager, profiled steps before a captured region
+    n_steps = K + W + G_STEPS + cpu_steps + 2 # + the steps that are replayed on the CPU oracle, + two that are looked at
+    per_seq = w.n_layers * w.n_kv_heads
+
+    # ---- the library's code objects are loaded by a throw-away run of the same calls on a small context of the same
+    # shape, so that the first step below times the eviction and not the loading
+    t0 = time.time()
+    small = ki.workload(args.workload, prefill=min(512, min(w.prefill)))
+    warm = Runner(small, args, 4, reserve, dev)
+    for s in range(4):
+        warm.step(s)
+    torch.cuda.synchronize()
+    assert kv.kvtrim_poll_error(warm.ctx) == 0
+    del warm
+    gc.collect()
+    torch.cuda.empty_cache()
+
+    r = Runner(w, args, n_steps, reserve, dev)
+    ctx, total0, B = r.ctx, r.total0, sum(w.budget)
+    log(f"[bench] {w.name}: prefill cache of {total0} entries, {2 * total0 * w.head_dim * 2 / 1e9:.2f} GB K/V; "
+        f"set up (with the code-object warm-up) in {time.time() - t0:.1f}s")
+
+    if args.pmc_calibration:                  # 2^28 floats in, 2^28 floats out, one elementwise copy kernel
+        ca = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        cb = torch.empty_like(ca)
+        cb.copy_(ca)
+        torch.cuda.synchronize()
+        del ca, cb
+        torch.cuda.empty_cache()
+
+    # ---- the first step evicts from the full prefill down to the budget: wall time between two events, and the
+    # sum of its kernels' own durations
+    all_kernels = (1 << kv.binding.N_KERNELS) - 1
+    kv.kvtrim_profile_begin(ctx, all_kernels)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    r.step(0)
+    e1.record()
+    torch.cuda.synchronize()
+    first_ms = e0.elapsed_time(e1)
+    prof0 = kv.kvtrim_profile_end(ctx)
+    first_kernels_ms = sum(ms for ms, _ in prof0.values())
+    assert kv.kvtrim_poll_error(ctx) == 0, "device-side error in the first step"
+    gc.collect()
+    torch.cuda.empty_cache()
+    for s in range(1, W):
+        r.step(s)
+    torch.cuda.synchronize()
+    n_ret = int(r.kept.sum().item())
+    n_cand = n_ret + w.nseg
+    log(f"[bench] first step (prefill -> budget): {first_ms:.3f} ms ({first_kernels_ms:.3f} ms in its "
+        f"{sum(n for _, n in prof0.values())} kernels); steady state: {n_cand} candidates, {n_ret} retained")
+
+    # ---- timed region: exactly K steps; the dominant kernels are bracketed by HIP events on the launch stream
+    mask = (1 << 8) | (1 << 10) | (1 << 13) | (1 << 30)   # k_cmp_copy, k_att_partial, k_cmp_attn, k_att_fused
+    if args.kernel_times:
+        mask = all_kernels                    # every kernel (the events then add to the step time)
+    kv.kvtrim_profile_begin(ctx, mask)
+    torch.cuda.synchronize()
+    if args.graph:
+        for s in range(W, W + G_STEPS):       # per-kernel durations: events cannot be recorded inside a capture
+            r.step(s)
+        torch.cuda.synchronize()
+        prof = kv.kvtrim_profile_end(ctx)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):         # the library only enqueues kernels on the current stream
+            for s in range(W + G_STEPS, W + G_STEPS + K):
+                r.step(s)
+        torch.cuda.synchronize()
+        t_begin = time.perf_counter()
+        graph.replay()
+        torch.cuda.synchronize()
+        t_end = time.perf_counter()
+    else:
+        t_begin = time.perf_counter()
+        for s in range(W, W + K):
+            r.step(s)
+        torch.cuda.synchronize()
+        t_end = time.perf_counter()
+        prof = kv.kvtrim_profile_end(ctx)
+    assert kv.kvtrim_poll_error(ctx) == 0, "device-side error in the timed region"
+    if args.kernel_times:
+        for name, (ms, n) in sorted(prof.items(), key=lambda kvp: -kvp[1][0]):
+            log(f"[bench]   {name:16s} {ms / n * 1e3:8.1f} us x {n}")
+    ms_per_step = (t_end - t_begin) * 1e3 / K
+    sel_paths = kv.kvtrim_select_path_counts(ctx)
+    next_step = W + G_STEPS + K               # first step after the timed region
+
+    # ---- byte models.  stage model: what the four stages move when each runs on its own (the benchmark's figure);
+    # moved: the compulsory bytes of the calls this run makes.
+    alg = algorithmic_bytes(w, n_cand, n_ret, args.horizon)
+    moved_rows = None
+    if args.inplace and not args.paged:
+        # how many rows an in-place step writes depends on the data: counted on the step after the timed region
+        s_extra = next_step
+        if s_extra % args.inplace == 0:
+            r.step(s_extra)
+            s_extra += 1
+        inp = r.inputs[s_extra]
+        kv.kvtrim_append(ctx, r.cur, inp["k_new"], inp["v_new"], inp["log_beta_new"], r.pos_news[s_extra], 1,
+                         log_tail_new=inp.get("log_tail_new"))
+        r.select(s_extra, r.cur)
+        torch.cuda.synchronize()
+        moved_rows = rows_moved_in_place(r.cur, r.keep)
+        kv.kvtrim_compact_attn_inplace(ctx, r.cur, r.keep, r.kept, r.spare[r.flip], inp["q"], 0, w.n_layers, r.scale, r.out, r.lse)
+        torch.cuda.synchronize()
+        next_step = s_extra + 1
+        log(f"[bench] in place: {moved_rows} of {n_ret} retained rows ({100.0 * moved_rows / n_ret:.1f} %) lie behind an eviction "
+            f"and are written; the others are only read")
+    moved = moved_bytes(w, args, n_cand, n_ret, moved_rows)
+    moved_total = sum(moved.values())
+    stage_model_bytes = None
+    nq_bytes = 6 * w.head_dim * w.n_seq * w.n_layers * w.n_q_heads
+    if args.paged:
+        dom, dom_bytes = "k_att_partial", moved["attend"]
+    elif args.unfused and args.inplace:
+        dom, dom_bytes = "k_att_partial", alg["attend"]
+    elif args.unfused:
+        dom, dom_bytes = "k_cmp_copy", alg["compact"]
+    else:
+        # The fused kernel does the work of stages 3 and 4 but reads K/V once.  Its roofline is priced on the bytes the
+        # fused operation cannot avoid: every retained entry read once and written once, the mask, q and out.
+        dom = "k_cmp_attn"
+        dom_bytes = alg["compact"] + n_cand + nq_bytes
+        stage_model_bytes = alg["compact"] + alg["attend"]
+        if args.inplace:
+            dom_bytes = [v for k, v in moved.items() if k.startswith("compact_attn")][0]
+            stage_model_bytes = None
+    if dom not in prof and "k_att_fused" in prof:   # large groups of query heads: the loop-shaped fused kernel, same bytes
+        dom = "k_att_fused"
+    if dom not in prof:                       # the cache is too large for the fused kernel: the library ran the two stages
+        dom, dom_bytes, stage_model_bytes = "k_cmp_copy", alg["compact"], None
+    dom_ms, dom_n = prof[dom]
+    dom_avg_ms = dom_ms / dom_n
+    achieved = dom_bytes / (dom_avg_ms * 1e-3) / 1e9
+    alg_total = sum(alg.values())
+    log(f"[bench] {ms_per_step:.4f} ms/step: {moved_total / (ms_per_step * 1e-3) / 1e9:.0f} GB/s on the {moved_total / 1e9:.3f} GB the "
+        f"calls move ({100 * moved_total / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS:.1f} % of peak); stage model "
+        f"{alg_total / 1e9:.3f} GB -> {alg_total / (ms_per_step * 1e-3) / 1e9:.0f} GB/s; {dom} {dom_avg_ms:.4f} ms "
+        f"({achieved:.0f} GB/s on its compulsory bytes)")
+    if not (args.separate_score_select or args.paged):
+        log(f"[bench] decode-step selections: {sel_paths[0]} from the candidate list, {sel_paths[1]} by the single-block fallback")
+    second = None
+    if args.unfused and args.inplace:
+        mv_ms, mv_n = prof["k_cmp_copy"]       # (the in-place row mover is bracketed under the row mover's name)
+        second = {"kernel": "k_cmp_move_inplace", "avg_launch_ms": mv_ms / mv_n}
+    elif args.unfused:
+        att_ms, att_n = prof["k_att_partial"]
+        second = {"kernel": "k_att_partial", "avg_launch_ms": att_ms / att_n,
+                  "achieved": alg["attend"] / (att_ms / att_n * 1e-3) / 1e9}
+
+    variant = "paged" if args.paged else "inplace" if args.inplace else "unfused" if args.unfused else "fused"
+    tag = {"long": "long_128k", "llama": "llama_32k", "vlm": "vlm", "tiny": "tiny", "multiturn": "multiturn"}[w.name] + \
+          {"fused": "", "paged": "_paged", "inplace": "_inplace", "unfused": "_unfused"}[variant]
+    calls = ("paged_append, paged_score, paged_select, paged_evict, paged_attn (paged layout: no K/V moved)" if args.paged else
+             ("append, " + ("score, select_global" if args.separate_score_select else "score_select") + ", " +
+              ("compact, decode_attn" if args.unfused and not args.inplace else
+               "compact_inplace, decode_attn" if args.unfused else
+               f"compact_attn_inplace (stages 3+4 fused inside the cache, {args.inplace} free slots per segment; every "
+               f"{args.inplace}th step an out-of-place compact_attn)" if args.inplace else
+               "compact_attn (stages 3+4 fused)")))
+    result = {
+        "metric": metric_name(w),
+        "value": 1e3 / ms_per_step,
+        "unit": "steps/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{w.name}: S{w.n_seq} L{w.n_layers} Hkv{w.n_kv_heads} Hq{w.n_q_heads} D{w.head_dim}, "
+                        f"{w.prefill[0] if w.n_seq == 1 else 'lengths ' + str(min(w.prefill)) + '..' + str(max(w.prefill))} prefilled, "
+                        f"B={B} ({n_cand} candidates/step, {n_ret} retained), "
+                        f"score lookahead horizon {args.horizon if args.horizon > 0 else 'infinite'}",
+            "stages": calls,
+            "first_step_ms": first_ms,
+            "first_step_kernels_ms": first_kernels_ms,
+            "first_step_note": "eviction from the whole prefill down to the budget, timed after a throw-away run of the same "
+                               "calls on a small context (code objects loaded); kernels_ms = sum of its kernels' durations",
+            "launch": "one HIP graph holding the K timed steps, replayed once" if args.graph else "eager launches",
+        },
+        "end_to_end": {
+            "moved_bytes_per_step": moved_total,
+            "moved_GBps": moved_total / (ms_per_step * 1e-3) / 1e9,
+            "frac_of_hbm_peak_on_moved_bytes": moved_total / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "moved_bytes_by_call": moved,
+            "moved_note": "compulsory HBM bytes of the calls this run makes (every array once per kernel that reads or writes it)",
+            "stage_model_bytes_per_step": alg_total,
+            "stage_model_GBps": alg_total / (ms_per_step * 1e-3) / 1e9,
+            "frac_of_hbm_peak_on_stage_model": alg_total / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "stage_model_bytes_by_stage": alg,
+            "stage_model_note": "a MODEL, not traffic: the bytes of the four stages run one by one (score 8 B, select 5 B per "
+                                "candidate; compact 2(4D+8) B, attend 4D B per retained entry); a fused call moves fewer",
+        },
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": measured_traffic(tag, dom),
+                     "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_avg_ms, "launches": dom_n,
+                     "stage_model_bytes_per_launch": stage_model_bytes,
+                     "stage_model_achieved": (stage_model_bytes / (dom_avg_ms * 1e-3) / 1e9) if stage_model_bytes else None,
+                     "second_kernel": second},
+    }
+    if not (args.separate_score_select or args.paged):
+        result["config"]["decode_step_selection"] = {"from_candidate_list": sel_paths[0], "single_block_fallback": sel_paths[1]}
+    if moved_rows is not None:
+        result["config"]["in_place"] = {"room": args.inplace, "rows_written_sampled": moved_rows, "rows_retained": n_ret}
+    if args.paged:
+        result["config"]["pages"] = {"page_size": kv.PAGE_SIZE, "n_pages": r.pc.n_pages,
+                                     "in_use_after_timed_region": int(r.pc.seg_pages.sum().item())}
+
+    # ---- CPU baseline: the oracle replays more steps of the same workload on the host cores, and the GPU's results of
+    # those steps are checked against it (selection / compaction bit-exact, attention 5e-3)
+    if cpu_steps:
+        import oracle
+        from harness import attn_error, compare_cache_contents, compare_caches, device_cache_to_host, sampled_step_check
+        from helpers import bf16_bits
+        budget_np = np.array(list(w.budget), np.int64)
+        live_bytes = 2 * n_ret * w.head_dim * 2
+        if live_bytes <= WHOLE_CACHE_PARITY_BYTES:
+            if args.paged:                      # the pages as the oracle's ragged cache: each segment in position order
+                from paged_harness import PagedHost
+                ph = PagedHost(r.pc)
+                hc = ph.as_ragged(oracle.Shape(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim), reserve)
+                del ph
+            else:
+                hc = device_cache_to_host(w, r.cur)
+            t_all, t_one, ok_sel, err = 0.0, 0.0, True, 0.0
+            n_all = cpu_steps - cpu_steps_1t
+            threads_all = oracle.threads()
+            for i, s in enumerate(range(next_step, next_step + cpu_steps)):
+                one = i >= n_all
+                oracle.set_threads(1 if one else threads_all)
+                inp = {k: v.cpu() for k, v in r.inputs[s].items()}
+                now = r.now0 + s + 1
+                pos_new = np.repeat(now, per_seq).astype(np.int32)
+                kb, vb, qb = bf16_bits(inp["k_new"]), bf16_bits(inp["v_new"]), bf16_bits(inp["q"])
+                lbn = inp["log_beta_new"].numpy()
+                ltn = inp["log_tail_new"].numpy() if args.horizon != 1 else None
+                t_cpu = time.perf_counter()
+                oracle.append(hc, kb, vb, lbn, pos_new, log_tail_new=ltn)
+                score_ref = oracle.score(hc, now)
+                keep_ref, kept_ref, thr_ref = oracle.select(hc, score_ref, budget_np)
+                hc = oracle.compact(hc, keep_ref, r.dst_cap, reserve)
+                out_ref, _ = oracle.attend(hc, qb, r.scale)
+                dt = time.perf_counter() - t_cpu
+                t_one, t_all = (t_one + dt, t_all) if one else (t_one, t_all + dt)
+                r.step(s)
+                torch.cuda.synchronize()
+                ok_sel = ok_sel and bool(np.array_equal(r.kept.cpu().numpy(), kept_ref)) \
+                    and bool(np.array_equal(r.thr.cpu().numpy().view(np.uint32), thr_ref))
+                err = max(err, attn_error(r.out.cpu().numpy(), out_ref))
+            oracle.set_threads(threads_all)
+            if args.paged:
+                ph = PagedHost(r.pc)
+                ok_cache = ph.structure_problems() == [] and ph.equals(hc)
+            elif args.inplace:                  # the segments keep their starts: contents are compared segment by segment
+                ok_cache = compare_cache_contents(device_cache_to_host(w, r.cur), hc)
+            else:
+                ok_cache = compare_caches(device_cache_to_host(w, r.cur), hc)
+            del hc
+            log(f"[bench] oracle on the host: {n_all} steps with {threads_all} threads in {t_all:.2f} s, {cpu_steps_1t} steps with one "
+                f"thread in {t_one:.2f} s; GPU vs oracle on those steps: selection equal={ok_sel}, final cache equal={ok_cache}, "
+                f"attention err={err:.2e}")
+            assert kv.kvtrim_poll_error(ctx) == 0 and ok_sel and ok_cache and err <= 5e-3, "GPU steps disagree with the oracle"
+            result["cpu_baseline"] = {
+                "value": n_all / t_all, "unit": "steps/s", "cores": threads_all, "kind": "oracle",
+                "sample": f"{n_all} full steps of the same workload after the timed region (append, score, full-sort select, "
+                          f"compact, fp64 attention); the attention loop runs on {threads_all} threads (OpenMP over segments), "
+                          "the other stages on one",
+                "single_thread": None if not cpu_steps_1t else {
+                    "value": cpu_steps_1t / t_one, "unit": "steps/s", "cores": 1,
+                    "sample": f"{cpu_steps_1t} further steps with every stage on one thread"}}
+            result["parity_on_sampled_step"] = {"steps": cpu_steps, "mode": "whole cache, every step",
+                                                "select_compact_bit_exact": ok_sel and ok_cache, "attn_max_norm_rel_err": err}
+        else:
+            # too large to replay whole on the host: one more step, selection and metadata whole, rows and attention sampled
+            assert not (args.paged or args.inplace), "sampled parity covers the out-of-place ragged step"
+            s = next_step
+            src = r.cur
+            t_cpu = time.perf_counter()
+            r.step(s)
+            torch.cuda.synchronize()
+            chk = sampled_step_check(w, src, r.now0 + s + 1, budget_np, reserve,
+                                     {"score": r.score, "keep": r.keep, "kept": r.kept, "thr": r.thr, "dst": r.cur, "out": r.out, "lse": r.lse},
+                                     q=r.inputs[s]["q"], scale=r.scale)
+            ok = all(chk[k] for k in ("score_equal", "keep_equal", "kept_equal", "thr_equal", "tables_equal", "metadata_equal", "rows_equal"))
+            log(f"[bench] sampled parity of one step ({time.perf_counter() - t_cpu:.1f} s): selection and metadata whole equal={ok}, "
+                f"rows and attention on {len(chk['sampled_segments'])} segments: err={chk['attn_err']:.2e}")
+            assert kv.kvtrim_poll_error(ctx) == 0 and ok and chk["attn_err"] <= 5e-3, "GPU step disagrees with the oracle"
+            result["parity_on_sampled_step"] = {"steps": 1, "mode": f"selection, counts, thresholds and compaction metadata whole; K/V rows "
+                                                f"and attention on {len(chk['sampled_segments'])} segments",
+                                                "select_compact_bit_exact": ok, "attn_max_norm_rel_err": chk["attn_err"]}
+        next_step += cpu_steps
+
+    # ---- the same steps with stages 3+4 done inside the cache (kvtrim_compact_attn_inplace), timed beside the metric's
+    # out-of-place step: ROOM free slots behind every segment, every ROOM-th step out of place to even them out (at
+    # least one such step falls inside the timed steps); the last step is checked against the oracle
+    K2 = min(K, 128)
+    ROOM = max(2, min(64, K2 // 2))
+    cap_room = n_ret + w.nseg * ROOM + 8
+    plain = not (brief or args.paged or args.unfused or args.inplace or args.graph or args.kernel_times or args.pmc_calibration
+                 or args.separate_score_select)
+    if plain and cap_room <= r.cap:
+        s0 = n_steps
+        extra, extra_now, extra_pos = [], [], []
+        for s in range(s0, s0 + K2 + 1):
+            extra.append(ki.decode_inputs(w, s, device=dev, horizon=args.horizon))
+            now = r.now0 + s + 1
+            extra_now.append(torch.from_numpy(now).to(dev))
+            extra_pos.append(torch.from_numpy(np.repeat(now, per_seq).astype(np.int32)).to(dev))
+        big = [kv.Cache.empty(w.nseg, w.head_dim, cap_room, dev, with_tail=args.horizon != 1) for _ in range(2)]
+        cur, other = r.cur, big[0]
+
+        def step_room(i, in_place):
+            nonlocal cur, other
+            inp = extra[i]
+            kv.kvtrim_append(ctx, cur, inp["k_new"], inp["v_new"], inp["log_beta_new"], extra_pos[i], 1,
+                             log_tail_new=inp.get("log_tail_new"))
+            kv.kvtrim_score_select(ctx, cur, extra_now[i], r.budget, r.score, r.keep, r.kept, r.thr, evict_hint=per_seq)
+            if in_place:
+                kv.kvtrim_compact_attn_inplace(ctx, cur, r.keep, r.kept, other, inp["q"], 0, w.n_layers, r.scale, r.out, r.lse)
+            else:
+                kv.kvtrim_compact_attn(ctx, cur, r.keep, r.kept, other, ROOM, inp["q"], 0, w.n_layers, r.scale, r.out, r.lse)
+                cur, other = other, (big[1] if other is big[0] else big[0])
+
+        step_room(0, False)                                        # into a cache with room behind every segment
+        torch.cuda.synchronize()
+        t_begin = time.perf_counter()
+        for i in range(1, K2):
+            step_room(i, i % ROOM != 0)
+        torch.cuda.synchronize()
+        ms_room = (time.perf_counter() - t_begin) * 1e3 / (K2 - 1)
+        n_oop = sum(1 for i in range(1, K2) if i % ROOM == 0)
+        parity_ip = None
+        if cpu_steps:                                              # the last step, in place, against the oracle
+            hc = device_cache_to_host(w, cur)
+            i = K2
+            inp = {k: v.cpu() for k, v in extra[i].items()}
+            now = r.now0 + s0 + i + 1
+            pos_new = np.repeat(now, per_seq).astype(np.int32)
+            oracle.append(hc, bf16_bits(inp["k_new"]), bf16_bits(inp["v_new"]), inp["log_beta_new"].numpy(), pos_new,
+                          log_tail_new=inp["log_tail_new"].numpy() if args.horizon != 1 else None)
+            keep_ref, kept_ref, thr_ref = oracle.select(hc, oracle.score(hc, now), budget_np)
+            hc = oracle.compact(hc, keep_ref, cap_room, 1)
+            out_ref, _ = oracle.attend(hc, bf16_bits(inp["q"]), r.scale)
+            step_room(i, i % ROOM != 0)
+            torch.cuda.synchronize()
+            ok = bool(np.array_equal(r.kept.cpu().numpy(), kept_ref)) and compare_cache_contents(device_cache_to_host(w, cur), hc)
+            err_ip = attn_error(r.out.cpu().numpy(), out_ref)
+            assert ok and err_ip <= 5e-3, "in-place step disagrees with the oracle"
+            parity_ip = {"select_compact_bit_exact": ok, "attn_max_norm_rel_err": err_ip, "in_place": i % ROOM != 0}
+            del hc
+        assert kv.kvtrim_poll_error(ctx) == 0 and int(r.kept.sum().item()) == n_ret and bool(torch.isfinite(r.out).all())
+        log(f"[bench] the same steps compacting in place: {ms_room:.4f} ms/step ({1e3 / ms_room:.0f} steps/s), "
+            f"{n_oop} of the {K2 - 1} timed steps out of place")
+        result["in_place_variant"] = {
+            "ms_per_step": ms_room, "value": 1e3 / ms_room, "unit": "steps/s", "steps": K2 - 1, "room": ROOM,
+            "out_of_place_steps_in_timed_region": n_oop, "parity_on_last_step": parity_ip,
+            "what": "append, score_select, compact_attn_inplace: a row moves only if an entry before it in its segment was evicted; "
+                    f"every {ROOM}th step is an out-of-place compact_attn that evens the free slots out"}
+        del big, extra
+    del r
+    gc.collect()
+    torch.cuda.empty_cache()
+    return result
+
+
+def summary_of(res):
+    """The figures of a side measurement that go into the main line."""
+    e = res["end_to_end"]
+    return {"workload": res["config"]["workload"], "calls": res["config"]["stages"], "steps": res["steps"],
+            "ms_per_step": res["ms_per_step"], "value": res["value"], "unit": res["unit"],
+            "first_step_ms": res["config"]["first_step_ms"], "first_step_kernels_ms": res["config"]["first_step_kernels_ms"],
+            "moved_bytes_per_step": e["moved_bytes_per_step"], "frac_of_hbm_peak_on_moved_bytes": e["frac_of_hbm_peak_on_moved_bytes"],
+            "stage_model_bytes_per_step": e["stage_model_bytes_per_step"],
+            "frac_of_hbm_peak_on_stage_model": e["frac_of_hbm_peak_on_stage_model"],
+            "dominant_kernel": {k: res["roofline"][k] for k in ("kernel", "avg_launch_ms", "achieved", "frac")},
+            "parity": res.get("parity_on_sampled_step"),
+            "decode_step_selection": res["config"].get("decode_step_selection")}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -300,10 +873,16 @@ def main():
     ap.add_argument("--horizon", type=int, default=1,
                     help="lookahead horizon of the score: 1 = the metric's form, 2 = the paper's inference default, 0 = infinite")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-steps", type=int, default=CPU_STEPS,
+                    help="steps the CPU oracle replays (and the GPU is checked on) after the timed region")
+    ap.add_argument("--only", action="store_true",
+                    help="time the named workload and variant only: no paged / other-workload side measurements behind the default run")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size reference for rocprofv3 --pmc counters")
     ap.add_argument("--unfused", action="store_true",
                     help="run stages 3 and 4 as two calls (kvtrim_compact, kvtrim_decode_attn) instead of the fused one")
+    ap.add_argument("--separate-score-select", action="store_true",
+                    help="run stages 1 and 2 as two calls (kvtrim_score, kvtrim_select_global) instead of kvtrim_score_select")
     ap.add_argument("--paged", action="store_true",
                     help="steady state on the paged layout: eviction frees slots of fixed-size pages and moves no K/V "
                          "(paged_append, paged_score, paged_select, paged_evict, paged_attn)")
@@ -327,25 +906,20 @@ def main():
     ap.add_argument("--inplace", type=int, default=0, metavar="ROOM",
                     help="compact inside the cache (kvtrim_compact_attn_inplace: rows move only behind an eviction) with ROOM "
                          "free slots behind every segment; every ROOM-th step is an out-of-place step that evens the room out")
-    ap.add_argument("--separate-score-select", action="store_true",
-                    help="run stages 1 and 2 as two calls (kvtrim_score, kvtrim_select_global) instead of kvtrim_score_select")
     ap.add_argument("--one-call", action="store_true",
                     help="with --chunk (ragged layout): the chunk step through kvtrim_append_compact, which moves the new rows "
                          "once, from the caller's buffers to the compacted cache")
     args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
     if args.one_call and (not args.chunk or args.paged):
         ap.error("--one-call needs --chunk and the ragged layout")
     if args.chunk:
-        if args.gpus != 1:
-            print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
-            sys.exit(2)
         if not 1 <= args.chunk <= 4096:
             ap.error("--chunk takes 1 .. 4096 tokens")
         return bench_chunk(args)
     if args.gate:
-        if args.gpus != 1:
-            print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
-            sys.exit(2)
         return bench_gate(args)
     if args.paged and args.unfused:
         ap.error("--paged and --unfused exclude each other")
@@ -353,380 +927,29 @@ def main():
         ap.error("--inplace takes a room of at least 2 slots and excludes --paged")
     if args.defrag_every and not args.paged:
         ap.error("--defrag-every needs --paged")
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
-        sys.exit(2)
 
-    import numpy as np
-    import torch
-    import kvtrim_inputs as ki
-    import paper_2605_09649_amd as kv
-
-    dev = "cuda:0"
-    torch.cuda.set_device(0)
-    w = ki.workload(args.workload, prefill=args.prefill)
-    reserve = args.inplace if args.inplace else 1                 # free slots behind every segment after an out-of-place step
-    K, W = args.steps, max(args.warmup, 1)
-    G_STEPS = 20 if args.graph else 0         # eager, profiled steps before a captured region
-    n_steps = K + W + G_STEPS + CPU_STEPS + 1 # + the extra steps that are replayed on the CPU oracle, + one that is looked at
-
-    t0 = time.time()
-    pre = ki.with_horizon(ki.prefill_cache(w, reserve=reserve, device=dev), args.horizon)
-    torch.cuda.synchronize()
-    total0 = sum(w.prefill) * w.n_layers * w.n_kv_heads
-    log(f"[bench] prefill cache: {total0} entries, {2 * total0 * w.head_dim * 2 / 1e9:.2f} GB K/V, "
-        f"generated in {time.time() - t0:.1f}s")
-
-    B = sum(w.budget)
-    dst_cap = min(B, total0 + n_steps * w.nseg) + w.nseg * reserve + 8
-    src = kv.Cache.from_dict(pre, dev)
-    spare, pc = [], None
-    if args.paged:
-        # room for the budget, one partly filled page per segment, and the pages that segments take while
-        # their own still hold scattered free slots elsewhere
-        n_pages = (min(B, total0 + n_steps * w.nseg) + kv.PAGE_SIZE - 1) // kv.PAGE_SIZE + 3 * w.nseg + 64
-        pc = kv.PagedCache(w.nseg, w.head_dim, n_pages, n_pages, dev, with_tail=args.horizon != 1)
-        dst_cap = n_pages * kv.PAGE_SIZE
-    else:
-        spare = [kv.Cache.empty(w.nseg, w.head_dim, dst_cap, dev, with_tail=args.horizon != 1) for _ in range(2)]
-    cap = max(src.cap, dst_cap)
-    ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, cap)
-    score = torch.zeros(cap, dtype=torch.float32, device=dev)
-    keep = torch.zeros(cap, dtype=torch.uint8, device=dev)
-    kept = torch.zeros(w.nseg, dtype=torch.int32, device=dev)
-    thr = torch.zeros(w.n_seq, dtype=torch.int32, device=dev)
-    budget = torch.tensor(list(w.budget), dtype=torch.int64, device=dev)
-    out = torch.zeros(w.n_seq, w.n_layers, w.n_q_heads, w.head_dim, dtype=torch.float32, device=dev)
-    lse = torch.zeros(w.n_seq, w.n_layers, w.n_q_heads, dtype=torch.float32, device=dev)
-    scale = 1.0 / math.sqrt(w.head_dim)
-    per_seq = w.n_layers * w.n_kv_heads
-
-    # every step's inputs are generated before the timed region and stay resident in HBM
-    inputs, nows, pos_news = [], [], []
-    now0 = np.array([t - 1 for t in w.prefill], np.int32)
-    for s in range(n_steps):
-        inputs.append(ki.decode_inputs(w, s, device=dev, horizon=args.horizon))
-        now = now0 + s + 1
-        nows.append(torch.from_numpy(now).to(dev))
-        pos_news.append(torch.from_numpy(np.repeat(now, per_seq).astype(np.int32)).to(dev))
-    torch.cuda.synchronize()
-
-    state = {"src": src, "flip": 0}
-
-    def step(s):
-        inp = inputs[s]
-        cur = state["src"]
-        if args.paged and s > 0:
-            kv.kvtrim_paged_append(ctx, pc, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos_news[s],
-                                   log_tail_new=inp.get("log_tail_new"))
-            kv.kvtrim_paged_score(ctx, pc, nows[s], score)
-            kv.kvtrim_paged_select(ctx, pc, score, budget, keep, kept, thr)
-            kv.kvtrim_paged_evict(ctx, pc, keep)
-            if args.defrag_every and s % args.defrag_every == 0:
-                kv.kvtrim_paged_defrag(ctx, pc)
-            kv.kvtrim_paged_attn(ctx, pc, inp["q"], 0, w.n_layers, scale, out, lse)
-            return
-        kv.kvtrim_append(ctx, cur, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos_news[s], 1,
-                         log_tail_new=inp.get("log_tail_new"))
-        if args.separate_score_select:
-            kv.kvtrim_score(ctx, cur, nows[s], score)
-            kv.kvtrim_select_global(ctx, cur, score, budget, keep, kept, thr)
-        else:                                   # first step: eviction from the whole prefill (hint 0: the radix passes)
-            kv.kvtrim_score_select(ctx, cur, nows[s], budget, score, keep, kept, thr, evict_hint=per_seq if s > 0 else 0)
-        if args.paged:                          # first step: the survivors of the prefill go into pages
-            kv.kvtrim_paged_build(ctx, cur, keep, kept, pc)
-            kv.kvtrim_paged_attn(ctx, pc, inp["q"], 0, w.n_layers, scale, out, lse)
-            state["src"] = None
-            return
-        dst = spare[state["flip"]]
-        if args.inplace and s > 0 and s % args.inplace:
-            # the other cache lends its arrays as parking space; the segments stay where they are
-            if args.unfused:                   # stage 3 alone in place, then the stand-alone attention on the same cache
-                kv.kvtrim_compact_inplace(ctx, cur, keep, kept, dst)
-                kv.kvtrim_decode_attn(ctx, cur, inp["q"], 0, w.n_layers, scale, out, lse)
-            else:
-                kv.kvtrim_compact_attn_inplace(ctx, cur, keep, kept, dst, inp["q"], 0, w.n_layers, scale, out, lse)
-            return
-        if args.unfused:
-            kv.kvtrim_compact(ctx, cur, keep, kept, dst, reserve)
-            kv.kvtrim_decode_attn(ctx, dst, inp["q"], 0, w.n_layers, scale, out, lse)
-        else:
-            kv.kvtrim_compact_attn(ctx, cur, keep, kept, dst, reserve, inp["q"], 0, w.n_layers, scale, out, lse)
-        state["src"] = dst
-        state["flip"] ^= 1
-
-    if args.pmc_calibration:                  # 2^28 floats in, 2^28 floats out, one elementwise copy kernel
-        ca = torch.ones(1 << 28, dtype=torch.float32, device=dev)
-        cb = torch.empty_like(ca)
-        cb.copy_(ca)
-        torch.cuda.synchronize()
-        del ca, cb
-        torch.cuda.empty_cache()
-
-    # ---- warm-up: the first step evicts from the full prefill down to the budget
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    step(0)
-    e1.record()
-    torch.cuda.synchronize()
-    first_ms = e0.elapsed_time(e1)
-    assert kv.kvtrim_poll_error(ctx) == 0, "device-side error in the first step"
-    del pre, src
-    torch.cuda.empty_cache()
-    for s in range(1, W):
-        step(s)
-    torch.cuda.synchronize()
-    n_ret = int(kept.sum().item())
-    n_cand = n_ret + w.nseg
-    log(f"[bench] first step (prefill -> budget): {first_ms:.3f} ms; steady state: {n_cand} candidates, {n_ret} retained")
-
-    # ---- timed region: exactly K steps; the dominant kernels are bracketed by HIP events on the launch stream
-    mask = (1 << 8) | (1 << 10) | (1 << 13) | (1 << 30)   # k_cmp_copy, k_att_partial, k_cmp_attn, k_att_fused
-    if args.kernel_times:
-        mask = (1 << kv.binding.N_KERNELS) - 1   # every kernel (the events then add to the step time)
-    kv.kvtrim_profile_begin(ctx, mask)
-    torch.cuda.synchronize()
-    if args.graph:
-        for s in range(W, W + G_STEPS):       # per-kernel durations: events cannot be recorded inside a capture
-            step(s)
-        torch.cuda.synchronize()
-        prof = kv.kvtrim_profile_end(ctx)
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):         # the library only enqueues kernels on the current stream
-            for s in range(W + G_STEPS, W + G_STEPS + K):
-                step(s)
-        torch.cuda.synchronize()
-        t_begin = time.perf_counter()
-        graph.replay()
-        torch.cuda.synchronize()
-        t_end = time.perf_counter()
-    else:
-        t_begin = time.perf_counter()
-        for s in range(W, W + K):
-            step(s)
-        torch.cuda.synchronize()
-        t_end = time.perf_counter()
-        prof = kv.kvtrim_profile_end(ctx)
-    assert kv.kvtrim_poll_error(ctx) == 0, "device-side error in the timed region"
-    if args.kernel_times:
-        for name, (ms, n) in sorted(prof.items(), key=lambda kvp: -kvp[1][0]):
-            log(f"[bench]   {name:16s} {ms / n * 1e3:8.1f} us x {n}")
-    ms_per_step = (t_end - t_begin) * 1e3 / K
-    sel_paths = kv.kvtrim_select_path_counts(ctx)
-    log(f"[bench] decode-step selections so far: {sel_paths[0]} from the candidate list, {sel_paths[1]} by the single-block fallback")
-    inplace_info = None
-    alg = algorithmic_bytes(w, n_cand, n_ret, args.horizon)
-    alg_total = sum(alg.values())
-    stage_model_bytes = None
-    if args.paged:
-        # no K/V moves: the step's compulsory bytes are the score (8 B), the selection (4 B score + 1 B mask)
-        # and the eviction (1 B mask + 4 B position) per candidate, and the attention's read of K, V and the
-        # position of every retained entry
-        alg = {"score": alg["score"], "select": alg["select"], "evict": 5 * n_cand,
-               "attend": alg["attend"] + 4 * n_ret}
-        alg_total = sum(alg.values())
-        dom, dom_bytes = "k_att_partial", alg["attend"]
-    elif args.unfused and args.inplace:
-        # stage 3 alone in place touches only the rows behind an eviction: the attention is the dominant kernel
-        dom, dom_bytes = "k_att_partial", alg["attend"]
-    elif args.unfused:
-        dom, dom_bytes = "k_cmp_copy", alg["compact"]
-    else:
-        # The fused kernel does the work of stages 3 and 4 but reads K/V once.  Its roofline is priced on
-        # the bytes the fused operation cannot avoid: every retained entry read once and written once
-        # (2 * (4D + 8) B), the mask (1 B per candidate), q and out (6D B per query head).  The stage-by-stage
-        # byte model (1040 + 512 B per retained entry) is reported beside it.
-        dom = "k_cmp_attn"
-        dom_bytes = alg["compact"] + n_cand + 6 * w.head_dim * w.n_seq * w.n_layers * w.n_q_heads
-        stage_model_bytes = alg["compact"] + alg["attend"]
-        if args.inplace:
-            # In place every retained entry is read once (4D + 8 B) and only the rows behind an eviction are written.
-            # How many those are depends on the data: they are counted on one more step after the timed region.
-            # One launch in ROOM is out of place.
-            s_extra = W + G_STEPS + K                              # the step right after the timed region
-            if s_extra % args.inplace == 0:
-                step(s_extra)                                      # (an out-of-place step falls here: look at the next one)
-                s_extra = None
-            moved = None
-            if s_extra is not None:
-                inp, cur = inputs[s_extra], state["src"]
-                kv.kvtrim_append(ctx, cur, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos_news[s_extra], 1,
-                                 log_tail_new=inp.get("log_tail_new"))
-                kv.kvtrim_score(ctx, cur, nows[s_extra], score)
-                kv.kvtrim_select_global(ctx, cur, score, budget, keep, kept, thr)
-                torch.cuda.synchronize()
-                moved = rows_moved_in_place(cur, keep)
-                kv.kvtrim_compact_attn_inplace(ctx, cur, keep, kept, spare[state["flip"]], inp["q"], 0, w.n_layers, scale, out, lse)
-                torch.cuda.synchronize()
-                log(f"[bench] in place: {moved} of {n_ret} retained rows ({100.0 * moved / n_ret:.1f} %) lie behind an eviction "
-                    f"and are written; the others are only read")
-            row_bytes = alg["compact"] // (2 * n_ret)
-            inplace_bytes = (alg["compact"] // 2 + row_bytes * (moved or 0) +
-                             6 * w.head_dim * w.n_seq * w.n_layers * w.n_q_heads)
-            dom_bytes = ((args.inplace - 1) * inplace_bytes + dom_bytes) // args.inplace
-            stage_model_bytes = None
-            alg = {"score": alg["score"], "select": alg["select"],
-                   "compact+attend (in place: every retained row read, the rows behind an eviction written)": dom_bytes}
-            alg_total = sum(alg.values())
-            inplace_info = {"room": args.inplace, "rows_written_sampled": moved, "rows_retained": n_ret}
-    if dom not in prof and "k_att_fused" in prof:   # large groups of query heads: the loop-shaped fused kernel, same bytes
-        dom = "k_att_fused"
-    if dom not in prof:                       # the cache is too large for the fused kernel: the library ran the two stages
-        dom, dom_bytes, stage_model_bytes = "k_cmp_copy", alg["compact"], None
-    dom_ms, dom_n = prof[dom]
-    dom_avg_ms = dom_ms / dom_n
-    achieved = dom_bytes / (dom_avg_ms * 1e-3) / 1e9
-    log(f"[bench] {ms_per_step:.4f} ms/step ({alg_total / (ms_per_step * 1e-3) / 1e9:.0f} GB/s algorithmic end to end); "
-        f"{dom} {dom_avg_ms:.4f} ms ({achieved:.0f} GB/s on its compulsory bytes)")
-    second = None
-    if args.unfused and args.inplace:
-        mv_ms, mv_n = prof["k_cmp_copy"]       # (the in-place row mover is bracketed under the row mover's name)
-        second = {"kernel": "k_cmp_move_inplace", "avg_launch_ms": mv_ms / mv_n}
-        log(f"[bench] in-place row mover (with one out-of-place launch in {args.inplace}) {mv_ms / mv_n:.4f} ms")
-    elif args.unfused:
-        att_ms, att_n = prof["k_att_partial"]
-        second = {"kernel": "k_att_partial", "avg_launch_ms": att_ms / att_n,
-                  "achieved": alg["attend"] / (att_ms / att_n * 1e-3) / 1e9}
-        log(f"[bench] k_att_partial {att_ms / att_n:.4f} ms ({second['achieved']:.0f} GB/s)")
-
-    result = {
-        "metric": "eviction+decode steps/sec and achieved HBM GB/s (% of peak), 32Lx8H 128K ctx",
-        "value": 1e3 / ms_per_step,
-        "unit": "steps/s",
-        "n_gpus": 1,
-        "steps": K,
-        "warmup": W,
-        "ms_per_step": ms_per_step,
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "bf16",
-        "data": "synthetic",
-        "config": {
-            "workload": f"{w.name}: S{w.n_seq} L{w.n_layers} Hkv{w.n_kv_heads} Hq{w.n_q_heads} D{w.head_dim}, "
-                        f"{w.prefill[0]} prefilled, B={B} ({n_cand} candidates/step, {n_ret} retained), "
-                        f"score lookahead horizon {args.horizon if args.horizon > 0 else 'infinite'}",
-            "stages": ("paged_append, paged_score, paged_select, paged_evict, paged_attn (paged layout: no K/V moved; "
-                       "five C-ABI calls per step)" if args.paged else
-                       "append, score, select_global, compact, decode_attn (five C-ABI calls per step)" if args.unfused else
-                       f"append, score, select_global, compact_attn_inplace (stages 3+4 fused inside the cache, {args.inplace} free "
-                       f"slots per segment; every {args.inplace}th step is an out-of-place compact_attn)" if args.inplace else
-                       "append, score, select_global, compact_attn (stages 3+4 fused; four C-ABI calls per step)"),
-            "first_step_ms": first_ms,
-            "launch": "one HIP graph holding the K timed steps, replayed once" if args.graph else "eager launches",
-        },
-        "end_to_end": {"algorithmic_bytes_per_step": alg_total, "achieved_GBps": alg_total / (ms_per_step * 1e-3) / 1e9,
-                       "frac_of_hbm_peak": alg_total / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                       "bytes_by_stage": alg},
-        "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC.get((w.name + ("-paged" if args.paged else "-inplace" if args.inplace else ""), dom)),
-                     "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_avg_ms, "launches": dom_n,
-                     "stage_model_bytes_per_launch": stage_model_bytes,
-                     "stage_model_achieved": (stage_model_bytes / (dom_avg_ms * 1e-3) / 1e9) if stage_model_bytes else None,
-                     "second_kernel": second},
-    }
-
-    if inplace_info:
-        result["config"]["in_place"] = inplace_info
-    if args.paged:
-        result["config"]["pages"] = {"page_size": kv.PAGE_SIZE, "n_pages": pc.n_pages,
-                                     "in_use_after_timed_region": int(pc.seg_pages.sum().item())}
-        log(f"[bench] pages in use after the timed region: {result['config']['pages']['in_use_after_timed_region']} of {pc.n_pages}")
-
-    # ---- CPU baseline: the oracle replays CPU_STEPS more steps of the same workload on the host cores, and the
-    # GPU's results of those steps are checked against it (selection/compaction bit-exact, attention 5e-3)
-    if not args.no_cpu_baseline:
-        import oracle
-        from harness import attn_error, compare_cache_contents, compare_caches, device_cache_to_host
-        from helpers import bf16_bits
-        if args.paged:                          # the pages as the oracle's ragged cache: each segment in position order
-            from paged_harness import PagedHost
-            ph = PagedHost(pc)
-            hc = ph.as_ragged(oracle.Shape(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim), reserve)
-            del ph
-        else:
-            hc = device_cache_to_host(w, state["src"])
-        budget_np = np.array(list(w.budget), np.int64)
-        cpu_s, ok_sel, err = 0.0, True, 0.0
-        first_cpu = W + G_STEPS + K + (1 if args.inplace else 0)   # (in place: one step was spent counting moved rows)
-        for s in range(first_cpu, first_cpu + CPU_STEPS):
-            inp = {k: v.cpu() for k, v in inputs[s].items()}
-            now = now0 + s + 1
-            pos_new = np.repeat(now, per_seq).astype(np.int32)
-            kb, vb, qb = bf16_bits(inp["k_new"]), bf16_bits(inp["v_new"]), bf16_bits(inp["q"])
-            lbn = inp["log_beta_new"].numpy()
-            ltn = inp["log_tail_new"].numpy() if args.horizon != 1 else None
-            t_cpu = time.perf_counter()
-            oracle.append(hc, kb, vb, lbn, pos_new, log_tail_new=ltn)
-            score_ref = oracle.score(hc, now)
-            keep_ref, kept_ref, thr_ref = oracle.select(hc, score_ref, budget_np)
-            hc = oracle.compact(hc, keep_ref, dst_cap, reserve)
-            out_ref, _ = oracle.attend(hc, qb, scale)
-            cpu_s += time.perf_counter() - t_cpu
-            step(s)
-            torch.cuda.synchronize()
-            ok_sel = ok_sel and bool(np.array_equal(kept.cpu().numpy(), kept_ref))
-            err = max(err, attn_error(out.cpu().numpy(), out_ref))
-        if args.paged:
-            ph = PagedHost(pc)
-            ok_cache = ph.structure_problems() == [] and ph.equals(hc)
-        elif args.inplace:                      # the segments keep their starts: contents are compared segment by segment
-            ok_cache = compare_cache_contents(device_cache_to_host(w, state["src"]), hc)
-        else:
-            ok_cache = compare_caches(device_cache_to_host(w, state["src"]), hc)
-        log(f"[bench] {CPU_STEPS} oracle steps on the host: {cpu_s:.2f} s; GPU vs oracle on those steps: kept equal={ok_sel}, "
-            f"final cache equal={ok_cache}, attention err={err:.2e}")
-        assert kv.kvtrim_poll_error(ctx) == 0 and ok_sel and ok_cache and err <= 5e-3, "GPU steps disagree with the oracle"
-        result["cpu_baseline"] = {"value": CPU_STEPS / cpu_s, "unit": "steps/s", "cores": oracle.threads(), "kind": "oracle",
-                                  "sample": f"{CPU_STEPS} full steps of the same workload after the timed region (append, score, "
-                                            "full-sort select, compact, fp64 attention); only the attention loop uses all cores "
-                                            "(OpenMP over segments), the other stages run on one"}
-        result["parity_on_sampled_step"] = {"steps": CPU_STEPS, "select_compact_bit_exact": ok_sel and ok_cache,
-                                            "attn_max_norm_rel_err": err}
-    # ---- the same steps with stages 3+4 done inside the cache (kvtrim_compact_attn_inplace), timed beside the metric's
-    # out-of-place step: ROOM free slots behind every segment, every ROOM-th step out of place to even them out
-    ROOM, K2 = 64, min(K, 128)
-    cap_room = n_ret + w.nseg * ROOM + 8
-    plain = not (args.paged or args.unfused or args.inplace or args.graph or args.kernel_times or args.pmc_calibration)
-    if plain and cap_room <= cap:
-        s0 = n_steps
-        extra, extra_now, extra_pos = [], [], []
-        for s in range(s0, s0 + K2 + 1):
-            extra.append(ki.decode_inputs(w, s, device=dev, horizon=args.horizon))
-            now = now0 + s + 1
-            extra_now.append(torch.from_numpy(now).to(dev))
-            extra_pos.append(torch.from_numpy(np.repeat(now, per_seq).astype(np.int32)).to(dev))
-        big = [kv.Cache.empty(w.nseg, w.head_dim, cap_room, dev, with_tail=args.horizon != 1) for _ in range(2)]
-        cur, other = state["src"], big[0]
-
-        def step_room(i, in_place):
-            nonlocal cur, other
-            inp = extra[i]
-            kv.kvtrim_append(ctx, cur, inp["k_new"], inp["v_new"], inp["log_beta_new"], extra_pos[i], 1,
-                             log_tail_new=inp.get("log_tail_new"))
-            kv.kvtrim_score(ctx, cur, extra_now[i], score)
-            kv.kvtrim_select_global(ctx, cur, score, budget, keep, kept, thr)
-            if in_place:
-                kv.kvtrim_compact_attn_inplace(ctx, cur, keep, kept, other, inp["q"], 0, w.n_layers, scale, out, lse)
-            else:
-                kv.kvtrim_compact_attn(ctx, cur, keep, kept, other, ROOM, inp["q"], 0, w.n_layers, scale, out, lse)
-                cur, other = other, (big[1] if other is big[0] else big[0])
-
-        step_room(0, False)                                        # into a cache with room behind every segment
-        torch.cuda.synchronize()
-        t_begin = time.perf_counter()
-        for i in range(1, K2 + 1):
-            step_room(i, i % ROOM != 0)
-        torch.cuda.synchronize()
-        ms_room = (time.perf_counter() - t_begin) * 1e3 / K2
-        assert kv.kvtrim_poll_error(ctx) == 0 and int(kept.sum().item()) == n_ret and bool(torch.isfinite(out).all())
-        log(f"[bench] the same steps compacting in place: {ms_room:.4f} ms/step ({1e3 / ms_room:.0f} steps/s)")
-        result["in_place_variant"] = {
-            "ms_per_step": ms_room, "value": 1e3 / ms_room, "unit": "steps/s", "steps": K2, "room": ROOM,
-            "what": "append, score, select_global, compact_attn_inplace: a row moves only if an entry before it in its segment "
-                    "was evicted; every 64th step is out of place (inside the timed steps); checked against the oracle by "
-                    "bench.py --inplace 64 and tests/test_gpu_inplace.py"}
+    result = run_decode(args)
+    default_run = not (args.only or args.paged or args.unfused or args.inplace or args.graph or args.kernel_times or
+                       args.pmc_calibration or args.separate_score_select or args.prefill or args.horizon != 1 or
+                       args.workload != "long")
+    if default_run:
+        # side measurements of the default run (each a short run of its own, after the metric's): the same workload on
+        # the paged layout, and the decode step of the other workloads; each with a parity check against the oracle
+        import copy
+        side = copy.copy(args)
+        side.steps, side.warmup, side.cpu_steps = min(args.steps, 50), 3, 0 if args.no_cpu_baseline else 4
+        side.paged = True
+        t0 = time.time()
+        result["paged_variant"] = summary_of(run_decode(side, brief=True))
+        log(f"[bench] paged variant: {result['paged_variant']['ms_per_step']:.4f} ms/step ({time.time() - t0:.0f} s)")
+        side.paged = False
+        result["other_workloads"] = {}
+        for name in ("tiny", "llama", "vlm", "multiturn"):
+            side.workload = name
+            side.steps = min(args.steps, 20 if name == "multiturn" else 50)
+            t0 = time.time()
+            result["other_workloads"][name] = summary_of(run_decode(side, brief=True))
+            log(f"[bench] {name}: {result['other_workloads'][name]['ms_per_step']:.4f} ms/step ({time.time() - t0:.0f} s)")
     print(json.dumps(result), flush=True)
 
 

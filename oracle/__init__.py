@@ -5,7 +5,7 @@ container.  Nothing here imports or is imported by the HIP path; only tests,
 the smoke check and the benchmark's ``cpu_baseline`` leg may use it.
 """
 from .host import (Gate, HostCache, Shape, build, gate_forward, lib, score, score_horizon, select, compact, attend, append, occupancy,
-                   key_of_score, threads)
+                   key_of_score, set_threads, threads)
 
 __all__ = ["Gate", "gate_forward", "HostCache", "Shape", "build", "lib", "score", "score_horizon", "select", "compact",
-           "attend", "append", "occupancy", "key_of_score", "threads"]
+           "attend", "append", "occupancy", "key_of_score", "set_threads", "threads"]

@@ -119,6 +119,11 @@ def threads():
     return int(lib().kvo_threads())
 
 
+def set_threads(n):
+    """Threads the oracle's attention loop uses from now on (its other stages always run on one)."""
+    lib().kvo_set_threads(C.c_int(int(n)))
+
+
 def key_of_score(s):
     return int(lib().kvo_key_of_score(C.c_float(float(s))))
 

@@ -430,6 +430,8 @@ void kvo_gate_forward(const kvo_gate *g, const uint16_t *x, int32_t n_tok, int32
 #ifdef _OPENMP
 #include <omp.h>
 int kvo_threads(void) { return omp_get_max_threads(); }
+/* Number of threads the attention loop may use from now on (for timing the oracle on one core and on all). */
+void kvo_set_threads(int n) { if (n >= 1) omp_set_num_threads(n); }
 #else
 int kvo_threads(void) { return 1; }
 #endif

@@ -338,3 +338,115 @@ def run_steps_inplace_both(w, steps, budget, room, cache_dict, now0, device="cud
         results.append(res)
         hc = hc_next
     return results
+
+
+def pick_segments(w, kept, n_random=8, seed=7):
+    """Segments to look at row by row: a few at random plus, for the first and the last sequence, the longest and
+    the shortest non-empty segment after the step (different sequences, extreme lengths)."""
+    rng = np.random.default_rng(seed)
+    per_seq = w.n_layers * w.n_kv_heads
+    pick = set(int(x) for x in rng.choice(w.nseg, min(n_random, w.nseg), replace=False))
+    for s in sorted({0, w.n_seq - 1}):
+        ks = kept[s * per_seq:(s + 1) * per_seq]
+        pick.add(s * per_seq + int(np.argmax(ks)))
+        nz = np.nonzero(ks)[0]
+        if len(nz):
+            pick.add(s * per_seq + int(nz[np.argmin(ks[nz])]))
+    return sorted(pick)
+
+
+def sampled_step_check(w, src, now, budget_np, reserve, gpu, q=None, scale=None, n_random=8, seed=7, new_rows=None,
+                       in_place_starts=None):
+    """One step at a size where the K/V rows cannot all go to the host: the oracle scores and selects on the metadata
+    alone (compared WHOLE: score bits, mask, per-segment counts, threshold keys), the destination's segment table and
+    per-entry metadata are compared WHOLE, K/V rows and the attention output on sampled segments.
+
+    src: the device cache the step selected on, after the append (its metadata holds the new tokens).
+    gpu: dict with the GPU's results - score, keep, kept, thr and, optionally, dst (device cache), out, lse.
+    new_rows: (k_new, v_new, n_new, old_len) when the rows of a segment's entries from old_len[g] on are in the
+      caller's new-token buffers and not in src (kvtrim_append_compact).
+    in_place_starts: segment starts of the destination when it was compacted in place (else the tight table).
+    Returns a dict of findings; everything that should be True / small is under its own key."""
+    D, G = w.head_dim, w.group
+    sh = oracle.Shape(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, D)
+    empty = np.zeros((0, D), np.uint16)
+    meta = oracle.HostCache.from_arrays(sh, empty, empty, src.log_beta.cpu().numpy(), src.pos.cpu().numpy(),
+                                        src.seg_start.cpu().numpy(), src.seg_len.cpu().numpy(),
+                                        log_tail=None if src.log_tail is None else src.log_tail.cpu().numpy())
+    score_ref = oracle.score(meta, np.asarray(now, np.int32))
+    keep_ref, kept_ref, thr_ref = oracle.select(meta, score_ref, np.asarray(budget_np, np.int64))
+    live = live_mask(meta)
+    n = meta.cap
+    res = {
+        "score_equal": bool(np.array_equal(gpu["score"][:n].cpu().numpy()[live].view(np.uint32), score_ref[live].view(np.uint32))),
+        "keep_equal": bool(np.array_equal(gpu["keep"][:n].cpu().numpy()[live], keep_ref[live])),
+        "kept_equal": bool(np.array_equal(gpu["kept"].cpu().numpy(), kept_ref)),
+        "thr_equal": bool(np.array_equal(gpu["thr"].cpu().numpy().view(np.uint32), thr_ref)),
+        "kept_total": int(kept_ref.sum()), "candidates": int(live.sum()),
+    }
+    dst = gpu.get("dst")
+    if dst is None:
+        return res
+    if in_place_starts is None:
+        exp_start = np.concatenate([[0], np.cumsum(kept_ref.astype(np.int64) + reserve)[:-1]])
+    else:
+        exp_start = np.asarray(in_place_starts, np.int64)
+    res["tables_equal"] = bool(np.array_equal(dst.seg_start.cpu().numpy(), exp_start)
+                               and np.array_equal(dst.seg_len.cpu().numpy(), kept_ref))
+    sel = keep_ref.astype(bool) & live
+    dlive = np.zeros(dst.cap, bool)
+    for s, m in zip(exp_start, kept_ref):
+        dlive[s:s + m] = True
+    ok = (np.array_equal(dst.log_beta.cpu().numpy()[dlive].view(np.uint32), meta.log_beta[sel].view(np.uint32))
+          and np.array_equal(dst.pos.cpu().numpy()[dlive], meta.pos[sel]))
+    if meta.log_tail is not None:
+        ok = ok and np.array_equal(dst.log_tail.cpu().numpy()[dlive].view(np.uint32), meta.log_tail[sel].view(np.uint32))
+    res["metadata_equal"] = bool(ok)
+    sample = pick_segments(w, kept_ref, n_random, seed)
+    res["sampled_segments"] = sample
+    rows_ok = True
+    rows_k, rows_v, lens, qs, out_rows, lse_rows = [], [], [], [], [], []
+    dev = dst.k.device
+    for g in sample:
+        s0, ln = int(meta.seg_start[g]), int(meta.seg_len[g])
+        m = keep_ref[s0:s0 + ln].astype(bool)
+        idx = np.nonzero(m)[0]
+        if new_rows is None:
+            ii = torch.from_numpy(s0 + idx).to(dev)
+            ks, vs = bf16_bits(src.k[ii]), bf16_bits(src.v[ii])
+        else:                                      # rows from old_len[g] on are in the caller's buffers
+            k_new, v_new, n_new, old_len = new_rows
+            old = idx[idx < old_len[g]]
+            new = idx[idx >= old_len[g]] - int(old_len[g])
+            io = torch.from_numpy(s0 + old).to(dev)
+            inn = torch.from_numpy(g * n_new + new).to(dev)
+            ks = np.concatenate([bf16_bits(src.k[io]), bf16_bits(k_new.reshape(-1, D)[inn])])
+            vs = np.concatenate([bf16_bits(src.v[io]), bf16_bits(v_new.reshape(-1, D)[inn])])
+        d0, dn = int(exp_start[g]), int(kept_ref[g])
+        rows_ok = rows_ok and np.array_equal(bf16_bits(dst.k[d0:d0 + dn]), ks) and np.array_equal(bf16_bits(dst.v[d0:d0 + dn]), vs)
+        rows_k.append(ks)
+        rows_v.append(vs)
+        lens.append(dn)
+    res["rows_equal"] = bool(rows_ok)
+    if q is not None:
+        q_host = bf16_bits(q).reshape(w.n_seq, w.n_layers, w.n_q_heads, D)
+        out_gpu = gpu["out"].cpu().numpy()
+        lse_gpu = gpu["lse"].cpu().numpy()
+        per_seq = w.n_layers * w.n_kv_heads
+        for g in sample:
+            seq, lh = divmod(g, per_seq)
+            layer, head = divmod(lh, w.n_kv_heads)
+            qs.append(q_host[seq, layer, head * G:(head + 1) * G])
+            out_rows.append(out_gpu[seq, layer, head * G:(head + 1) * G])
+            lse_rows.append(lse_gpu[seq, layer, head * G:(head + 1) * G])
+        starts = np.concatenate([[0], np.cumsum(lens)[:-1]]).astype(np.int64)
+        n_tot = int(np.sum(lens))
+        small_shape = oracle.Shape(1, 1, len(sample), len(sample) * G, D)
+        small = oracle.HostCache.from_arrays(small_shape, np.concatenate(rows_k).reshape(-1, D), np.concatenate(rows_v).reshape(-1, D),
+                                             np.zeros(n_tot, np.float32), np.zeros(n_tot, np.int32), starts, np.array(lens, np.int32))
+        ref, lse_ref = oracle.attend(small, np.concatenate(qs), scale)
+        res["attn_err"] = attn_error(np.concatenate(out_rows), ref[0, 0])
+        lr, lg = lse_ref[0, 0], np.concatenate(lse_rows)
+        fin = np.isfinite(lr)
+        res["lse_err"] = float(np.abs(lg[fin] - lr[fin]).max()) if fin.any() else 0.0
+    return res
