@@ -20,7 +20,14 @@
  *    in a HIP graph).  Conditions only the device can see (a destination too
  *    small, a `kept` array that disagrees with the mask) set a sticky device flag;
  *    the kernel that finds the condition writes nothing out of bounds, and later
- *    kernels of the same call return early.  kvtrim_poll_error reads and clears it.
+ *    kernels return early.  The flag is STICKY ACROSS CALLS: while it is set, the
+ *    compaction and attention kernels of every later call on the context (also the
+ *    replays of a captured graph) do nothing and leave their outputs as they were,
+ *    although the host-side status of those calls is KVTRIM_OK - the state the flag
+ *    describes is one the next kernels cannot safely build on.  kvtrim_poll_error
+ *    reads and clears it: poll after the calls whose device-side errors matter
+ *    (an append that may run out of room, a compaction into a tight destination)
+ *    and at least once per batch of replayed steps.
  *  - A context owns one workspace (allocated in kvtrim_create) that every call
  *    reuses: calls on one context must be ordered on one stream and come from one
  *    host thread at a time (the context also keeps the last error text and the

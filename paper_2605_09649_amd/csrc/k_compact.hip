@@ -56,7 +56,8 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_prefix(CacheView src, cons
             const int len = src.seg_len[i];
             const int64_t st = src.seg_start[i];
             const int kp = kept[i];
-            if (len < 0 || st < 0 || st + len > src.cap) s_bad_layout = 1;
+            const int64_t nxt = i + 1 < nseg ? src.seg_start[i + 1] : src.cap;
+            if (len < 0 || st < 0 || st + len > src.cap || st + len > nxt) s_bad_layout = 1;
             if (kp < 0 || kp > len) s_bad_kept = 1;
             nch = len > 0 ? ((int64_t)len + CMP_CHUNK - 1) / CMP_CHUNK : 0;
             need = ((int64_t)kp + reserve + align - 1) / align * align;
@@ -67,7 +68,8 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_prefix(CacheView src, cons
         const int64_t ex_e = block_excl_scan<int64_t>(need, lds64, &tot_e);
         if (i < nseg) {
             ws.cmp_chunk_prefix[i] = (int32_t)min(chunks + ex_c, (int64_t)0x7fffffff);
-            if (!inplace) dst.seg_start[i] = entries + ex_e;
+            // (parked in the workspace: the destination is written only once the capacity check below has passed)
+            if (!inplace) ws.pg_seg_start[i] = entries + ex_e;
         }
         chunks += tot_c;
         entries += tot_e;
@@ -89,6 +91,10 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_prefix(CacheView src, cons
             ws.cmp_chunk_prefix[nseg] = (int32_t)chunks;
             if (run > 0) ws.att_chunk_prefix[nseg] = (int32_t)runs;
         }
+    }
+    if (!inplace && !(bad_layout || bad_kept || entries > dst.cap)) {
+        __syncthreads();                                          // the parked starts are this block's own writes
+        for (int i = tid; i < nseg; i += SCAN_THREADS) dst.seg_start[i] = ws.pg_seg_start[i];
     }
 }
 
@@ -162,7 +168,8 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const 
         int64_t acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // chunks_before, dst_before, dst_total, chunks_total, bad_layout, bad_kept, runs_before, runs_total
         if (tid < nseg) {
             const int i = tid;
-            acc[4] |= (o_len < 0 || o_st < 0 || o_st + o_len > src.cap);
+            const int64_t o_nxt = i + 1 < nseg ? src.seg_start[i + 1] : src.cap;
+            acc[4] |= (o_len < 0 || o_st < 0 || o_st + o_len > src.cap || o_st + o_len > o_nxt);
             acc[5] |= (o_kp < 0 || o_kp > o_len);
             const int64_t nc = o_len > 0 ? ((int64_t)o_len + CMP_CHUNK - 1) / CMP_CHUNK : 0;
             const int64_t need = ((int64_t)o_kp + reserve + align - 1) / align * align;   // align = 1 unless pages are built

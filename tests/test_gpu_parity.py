@@ -422,6 +422,57 @@ def test_device_side_errors_are_reported_and_nothing_overflows():
     assert kv.kvtrim_poll_error(ctx) == -6                               # KVTRIM_ELAYOUT
 
 
+@pytest.mark.parametrize("nseg", [6, 1500])
+def test_compaction_rejects_overlapping_segments_and_leaves_the_destination_alone(nseg):
+    # a segment that runs into its successor (still inside the buffers) must not reach the row movers, in either
+    # form of the compaction scan (one block per segment summing all segments itself: up to 1024 segments; a prefix
+    # kernel first: more); and a destination that is too small is left untouched, segment table included
+    w = wl(1, 1, nseg, 1, 64)
+    seg_len = [20] * nseg
+    c, now = ki.ragged_cache(w, seg_len, reserve=1, salt=3)
+    cap = c["cap"]
+    ctx = kv.Context(1, 1, nseg, nseg, 64, cap + 64)
+    src = kv.Cache.from_dict(c, DEV)
+    keep = torch.ones(cap, dtype=torch.uint8, device=DEV)
+    kept = torch.tensor(seg_len, dtype=torch.int32, device=DEV)
+    q = torch.zeros(1, 1, nseg, 64, dtype=torch.bfloat16, device=DEV)
+    out = torch.zeros(1, 1, nseg, 64, dtype=torch.float32, device=DEV)
+
+    def fresh(n):
+        d = kv.Cache.empty(nseg, 64, n, DEV)
+        d.k.fill_(1.0)
+        d.seg_start.fill_(-7)
+        d.seg_len.fill_(-7)
+        return d
+
+    small = fresh(sum(seg_len) + nseg - 1)                        # one slot short
+    for call in ("compact", "compact_attn"):
+        if call == "compact":
+            kv.kvtrim_compact(ctx, src, keep, kept, small, 1)
+        else:
+            kv.kvtrim_compact_attn(ctx, src, keep, kept, small, 1, q, 0, 1, 0.125, out)
+        assert kv.kvtrim_poll_error(ctx) == -4                    # KVTRIM_ECAP
+        assert torch.all(small.k == 1.0) and torch.all(small.seg_start == -7) and torch.all(small.seg_len == -7)
+    lens = src.seg_len.clone()
+    lens[2] = 25                                                  # 4 entries into segment 3's range
+    bad = kv.Cache(src.k, src.v, src.log_beta, src.pos, src.seg_start, lens)
+    kept_bad = kept.clone()
+    kept_bad[2] = 25
+    big = fresh(cap + 64)
+    for call in ("compact", "compact_attn", "inplace"):
+        if call == "compact":
+            kv.kvtrim_compact(ctx, bad, keep, kept_bad, big, 1)
+        elif call == "compact_attn":
+            kv.kvtrim_compact_attn(ctx, bad, keep, kept_bad, big, 1, q, 0, 1, 0.125, out)
+        else:
+            spare = kv.Cache.empty(nseg, 64, cap, DEV)
+            before = bad.k.clone()
+            kv.kvtrim_compact_attn_inplace(ctx, bad, keep, kept_bad, spare, q, 0, 1, 0.125, out)
+            assert torch.equal(bad.k, before)
+        assert kv.kvtrim_poll_error(ctx) == -6                    # KVTRIM_ELAYOUT
+        assert torch.all(big.k == 1.0) and torch.all(big.seg_len == -7)
+
+
 def test_host_side_argument_checks():
     ctx = kv.Context(1, 1, 2, 4, 64, 100)
     c = kv.Cache.empty(2, 64, 100, DEV)
