@@ -402,6 +402,18 @@ class Runner:
             kv.kvtrim_paged_attn(ctx, pc, inp["q"], 0, w.n_layers, scale, out, lse)
             return
         cur = self.cur
+        if not (a.paged or a.inplace or a.unfused or a.separate_score_select or a.separate_calls):
+            # the whole step in one call (three kernels for a decode step; the first step, with hint 0, runs the
+            # calls it stands for one after the other)
+            dst = self.spare[self.flip]
+            kv.kvtrim_decode_step(ctx, cur, inp["k_new"], inp["v_new"], inp["log_beta_new"], self.pos_news[s], 1, self.nows[s],
+                                  self.budget, self.score, self.keep, self.kept, dst, self.reserve, inp["q"], 0, w.n_layers,
+                                  scale, out, lse, thr_key_out=self.thr, log_tail_new=inp.get("log_tail_new"),
+                                  evict_hint=self.per_seq if s > 0 else 0)
+            self.cur = dst
+            self.src = None
+            self.flip ^= 1
+            return
         kv.kvtrim_append(ctx, cur, inp["k_new"], inp["v_new"], inp["log_beta_new"], self.pos_news[s], 1,
                          log_tail_new=inp.get("log_tail_new"))
         self.select(s, cur)
@@ -437,10 +449,13 @@ def moved_bytes(w, a, n_cand, n_ret, rows_written_in_place=None):
     tail = 0 if a.horizon == 1 else 4
     R = 4 * D + 8 + tail
     nq = w.n_seq * w.n_layers * w.n_q_heads
+    one_call = not (a.paged or a.inplace or a.unfused or a.separate_score_select or a.separate_calls)
     m = {"append": 2 * R * w.nseg}
     if a.separate_score_select or a.paged:
         m["score"] = (8 + tail + 4) * n_cand                       # log beta, position (, tail) in; score out
         m["select"] = (3 * 4 + 4 + 1) * n_cand                     # three histogram passes and the mask pass read the score; mask out
+    elif one_call:
+        m["score + select (inside decode_step)"] = (8 + tail + 4 + 1) * n_cand   # one scoring pass (score out); the mask is written by the row mover
     else:
         m["score_select"] = (8 + tail + 4 + 4 + 1) * n_cand        # one scoring pass (score out), one mask pass (score in, mask out)
     if a.paged:
@@ -455,6 +470,8 @@ def moved_bytes(w, a, n_cand, n_ret, rows_written_in_place=None):
     elif a.unfused:
         m["compact"] = n_cand + 2 * R * n_ret
         m["decode_attn"] = 4 * D * n_ret + 6 * D * nq
+    elif one_call:
+        m["compact + attend (inside decode_step)"] = 2 * R * n_ret + 6 * D * nq   # every retained entry in and out once; q in, out out
     else:
         m["compact_attn"] = n_cand + 2 * R * n_ret + 6 * D * nq    # mask in; every retained entry in and out once; q in, out out
     return m
@@ -599,8 +616,8 @@ def run_decode(args, brief=False):
     else:
         # The fused kernel does the work of stages 3 and 4 but reads K/V once.  Its roofline is priced on the bytes the
         # fused operation cannot avoid: every retained entry read once and written once, the mask, q and out.
-        dom = "k_cmp_attn"
-        dom_bytes = alg["compact"] + n_cand + nq_bytes
+        dom = "k_cmp_attn"                      # (the one-call step's row mover is bracketed under the same name)
+        dom_bytes = alg["compact"] + n_cand + nq_bytes   # mask in (separate calls) / out (one call)
         stage_model_bytes = alg["compact"] + alg["attend"]
         if args.inplace:
             dom_bytes = [v for k, v in moved.items() if k.startswith("compact_attn")][0]
@@ -631,7 +648,9 @@ def run_decode(args, brief=False):
     variant = "paged" if args.paged else "inplace" if args.inplace else "unfused" if args.unfused else "fused"
     tag = {"long": "long_128k", "llama": "llama_32k", "vlm": "vlm", "tiny": "tiny", "multiturn": "multiturn"}[w.name] + \
           {"fused": "", "paged": "_paged", "inplace": "_inplace", "unfused": "_unfused"}[variant]
-    calls = ("paged_append, paged_score, paged_select, paged_evict, paged_attn (paged layout: no K/V moved)" if args.paged else
+    one_call = not (args.paged or args.inplace or args.unfused or args.separate_score_select or args.separate_calls)
+    calls = ("decode_step (append, stages 1-4 in one call; three kernels per decode step)" if one_call else
+             "paged_append, paged_score, paged_select, paged_evict, paged_attn (paged layout: no K/V moved)" if args.paged else
              ("append, " + ("score, select_global" if args.separate_score_select else "score_select") + ", " +
               ("compact, decode_attn" if args.unfused and not args.inplace else
                "compact_inplace, decode_attn" if args.unfused else
@@ -783,7 +802,7 @@ def run_decode(args, brief=False):
     ROOM = max(2, min(64, K2 // 2))
     cap_room = n_ret + w.nseg * ROOM + 8
     plain = not (brief or args.paged or args.unfused or args.inplace or args.graph or args.kernel_times or args.pmc_calibration
-                 or args.separate_score_select)
+                 or args.separate_score_select or args.separate_calls)
     if plain and cap_room <= r.cap:
         s0 = n_steps
         extra, extra_now, extra_pos = [], [], []
@@ -881,6 +900,8 @@ def main():
                     help="also run one plain 1 GiB device copy, the known-size reference for rocprofv3 --pmc counters")
     ap.add_argument("--unfused", action="store_true",
                     help="run stages 3 and 4 as two calls (kvtrim_compact, kvtrim_decode_attn) instead of the fused one")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="run the step as append, score_select, compact_attn instead of the one call kvtrim_decode_step")
     ap.add_argument("--separate-score-select", action="store_true",
                     help="run stages 1 and 2 as two calls (kvtrim_score, kvtrim_select_global) instead of kvtrim_score_select")
     ap.add_argument("--paged", action="store_true",
@@ -930,7 +951,7 @@ def main():
 
     result = run_decode(args)
     default_run = not (args.only or args.paged or args.unfused or args.inplace or args.graph or args.kernel_times or
-                       args.pmc_calibration or args.separate_score_select or args.prefill or args.horizon != 1 or
+                       args.pmc_calibration or args.separate_score_select or args.separate_calls or args.prefill or args.horizon != 1 or
                        args.workload != "long")
     if default_run:
         # side measurements of the default run (each a short run of its own, after the metric's): the same workload on

@@ -268,6 +268,29 @@ kvtrim_status kvtrim_append(kvtrim_ctx *ctx, kvtrim_cache *c, const void *k_new,
                             const float *log_beta_new, const float *log_tail_new, const int32_t *pos_new,
                             int32_t n_new, void *hip_stream);
 
+/* A decode step on the ragged layout in one call (Sec. 4.2: the new token is cached, every entry rescored, the
+ * cache evicted down to the budget and attended).  Leaves in src, score_out, keep_out, kept_out, thr_key_out, dst, out
+ * and lse exactly what
+ *     kvtrim_append(src, new tokens) -> kvtrim_score_select(src, now, budget, evict_hint)
+ *     -> kvtrim_compact_attn(src -> dst, reserve, q)
+ * leave there (bit for bit in everything but out / lse, which agree within the attention tolerance: the split of
+ * the softmax sums is the same, so in practice they are equal too).  Arguments as in those three calls; keep_out is
+ * required.  With a small evict_hint (see kvtrim_score_select) and up to 5 query heads per KV head (4 at head_dim
+ * 64), at most 1024 segments per sequence, 1024 sequences and 16 new tokens per segment the step is THREE kernels:
+ * one scores, lists the eviction candidates and - in each sequence's last block - ranks them, counts the evicted
+ * entries per segment and leaves the destination's segment table, a destination offset for every chunk of 128
+ * entries and the mask bytes of the few chunks that lose entries (further blocks of the same launch append the new
+ * tokens); one moves every surviving row while using it for the attention of its segment (no mask pass, no
+ * compaction scan: it writes the mask bytes of the chunks that lose nothing itself); one merges the partial
+ * attention results.  Any other shape or hint runs the three calls one after the other.  Device-side errors as in
+ * the three calls. */
+kvtrim_status kvtrim_decode_step(kvtrim_ctx *ctx, kvtrim_cache *src, const void *k_new, const void *v_new,
+                                 const float *log_beta_new, const float *log_tail_new, const int32_t *pos_new,
+                                 int32_t n_new, const int32_t *now, const int64_t *budget, float *score_out,
+                                 uint8_t *keep_out, int32_t *kept_out, uint32_t *thr_key_out, kvtrim_cache *dst,
+                                 int32_t reserve, const void *q, int32_t layer_begin, int32_t layer_end,
+                                 float softmax_scale, float *out, float *lse, int64_t evict_hint, void *hip_stream);
+
 /* A chunk of a prefill on the ragged layout in one call (the multi-turn flow of Sec. 4.2 / Sec. 5:
  * after every appended chunk of tokens the cache is rescored, selected and compacted).  Leaves in
  * score_out, keep_out, kept_out, thr_key_out and dst exactly what

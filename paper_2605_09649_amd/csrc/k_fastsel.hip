@@ -1,4 +1,5 @@
-// Stages 1 + 2 for decode steps (Sec. 4.2: Eq. global_score and the global eviction rule) in two kernels.
+// Stages 1 + 2 for decode steps (Sec. 4.2: Eq. global_score and the global eviction rule) in two kernels; the
+// first of them, in its STEP form, is also the first kernel of the one-call decode step.
 //
 // A decode step evicts a handful of entries per sequence - as many as it appended - so the selection is the
 // search for the FEW LOWEST entries of the total order (key descending, segment ascending, position ascending),
@@ -39,6 +40,40 @@ __device__ __forceinline__ int seg_checked_len(const CacheView& c, int g, int ns
         return 0;
     }
     return len;
+}
+
+// A segment as the kernels see it.  STEP: its entries [len_old, len) are this step's new tokens - up to the first
+// padding row (negative position), none if the segment has no room for them (kvtrim_append's rule) - whose
+// metadata is read from the new-token buffers by every block, never from the cache.
+struct SegView {
+    int64_t start;
+    int len_old;
+    int len;
+};
+
+template <bool STEP>
+__device__ __forceinline__ SegView seg_view(const CacheView& c, int g, int nseg, const StepArgs& sa, bool* bad, bool* nocap) {
+    SegView v;
+    const int len = c.seg_len[g];
+    const int64_t st = c.seg_start[g];
+    const int64_t nxt = g + 1 < nseg ? c.seg_start[g + 1] : c.cap;
+    v.start = st;
+    if (len < 0 || st < 0 || st + len > c.cap || st + len > nxt) {
+        *bad = true;
+        v.len_old = v.len = 0;
+        return v;
+    }
+    v.len_old = v.len = len;
+    if (STEP) {
+        int cnt = 0;
+        while (cnt < sa.n_new && sa.pos_new[(int64_t)g * sa.n_new + cnt] >= 0) ++cnt;
+        if (st + len + cnt > nxt || nxt > c.cap) {
+            if (cnt) *nocap = true;
+            cnt = 0;
+        }
+        v.len = len + cnt;
+    }
+    return v;
 }
 
 // a is evicted before b: lower key first; among equal keys the later (segment, position) first
@@ -115,39 +150,60 @@ __device__ __forceinline__ void walk_from_top(ResolveShared* sm, int64_t rank) {
 // Where the key of an entry comes from: computed from log beta and the position (SCORE: stage 1 fused, Eq.
 // global_score in log domain - one fp32 multiply, or one fused multiply-add with the cached horizon tail) or
 // read from the caller's score array.  Both are inputs of the call, so any block may read any entry at any time.
-template <bool SCORE>
+template <bool SCORE, bool STEP>
 struct KeySource {
     const float* score_in;
     const float* lb;
     const float* lt;
     const int32_t* pos;
+    const float* lb_new;
+    const float* lt_new;
+    const int32_t* pos_new;
+    int n_new;
     int t1;
-    __device__ __forceinline__ float score_at(int64_t e) const {
-        if (!SCORE) return score_in[e];
-        const float dt = (float)(t1 - pos[e]);
-        return lt ? __fmaf_rn(dt, lb[e], lt[e]) : __fmul_rn(dt, lb[e]);
+    __device__ __forceinline__ int pos_at(int g, const SegView& v, int j) const {
+        if (STEP && j >= v.len_old) return pos_new[(int64_t)g * n_new + (j - v.len_old)];
+        return pos[v.start + j];
+    }
+    __device__ __forceinline__ float score_at(int g, const SegView& v, int j) const {
+        if (!SCORE) return score_in[v.start + j];
+        float b, t = 0.f;
+        int p;
+        if (STEP && j >= v.len_old) {
+            const int64_t i = (int64_t)g * n_new + (j - v.len_old);
+            p = pos_new[i];
+            b = lb_new[i];
+            if (lt) t = lt_new[i];
+        } else {
+            const int64_t e = v.start + j;
+            p = pos[e];
+            b = lb[e];
+            if (lt) t = lt[e];
+        }
+        const float dt = (float)(t1 - p);
+        return lt ? __fmaf_rn(dt, b, t) : __fmul_rn(dt, b);
     }
 };
 
 // One digit of a most-significant-digit radix select over all entries of the sequence, by this block alone.
-template <int PASS, bool SCORE>
-__device__ __forceinline__ void slow_pass(const KeySource<SCORE>& ks, const CacheView& c, const Shape& sh, int seq,
-                                          uint32_t prefix, ResolveShared* sm) {
+template <int PASS, bool SCORE, bool STEP>
+__device__ __forceinline__ void slow_pass(const KeySource<SCORE, STEP>& ks, const CacheView& c, const Shape& sh,
+                                          const StepArgs& sa, int seq, uint32_t prefix, ResolveShared* sm) {
     constexpr int NB = PASS == 2 ? 1024 : 2048;
     const int tid = threadIdx.x;
     __syncthreads();
     for (int i = tid; i < NB; i += FAST_THREADS) sm->h[i] = 0;
     __syncthreads();
     for (int g = seq * sh.segs_per_seq; g < (seq + 1) * sh.segs_per_seq; ++g) {
-        int64_t start;
-        bool bad = false;
-        const int len = seg_checked_len(c, g, sh.nseg, &start, &bad);
+        bool bad = false, nocap = false;
+        const SegView v = seg_view<STEP>(c, g, sh.nseg, sa, &bad, &nocap);
+        const int len = v.len;
         for (int j0 = tid; j0 < len; j0 += FAST_THREADS * FAST_BATCH) {
             float sv[FAST_BATCH];
 #pragma unroll
             for (int u = 0; u < FAST_BATCH; ++u) {
                 const int j = j0 + u * FAST_THREADS;
-                sv[u] = j < len ? ks.score_at(start + j) : 0.f;
+                sv[u] = j < len ? ks.score_at(g, v, j) : 0.f;
             }
 #pragma unroll
             for (int u = 0; u < FAST_BATCH; ++u) {
@@ -161,19 +217,19 @@ __device__ __forceinline__ void slow_pass(const KeySource<SCORE>& ks, const Cach
 
 // Key of the entry of rank `rank` (1-based, descending key order) of the sequence; *rank_in = its rank among the
 // entries with that key, *ties = how many entries have that key.
-template <bool SCORE>
-__device__ __forceinline__ uint32_t slow_radix(const KeySource<SCORE>& ks, const CacheView& c, const Shape& sh,
-                                               int seq, int64_t rank, ResolveShared* sm, int64_t* rank_in,
-                                               uint32_t* ties) {
-    slow_pass<0>(ks, c, sh, seq, 0, sm);
+template <bool SCORE, bool STEP>
+__device__ __forceinline__ uint32_t slow_radix(const KeySource<SCORE, STEP>& ks, const CacheView& c, const Shape& sh,
+                                               const StepArgs& sa, int seq, int64_t rank, ResolveShared* sm,
+                                               int64_t* rank_in, uint32_t* ties) {
+    slow_pass<0>(ks, c, sh, sa, seq, 0, sm);
     walk_from_top<2048>(sm, rank);
     uint32_t prefix = (uint32_t)sm->digit;
     rank = sm->rank_in;
-    slow_pass<1>(ks, c, sh, seq, prefix, sm);
+    slow_pass<1>(ks, c, sh, sa, seq, prefix, sm);
     walk_from_top<2048>(sm, rank);
     prefix = (prefix << RADIX_BITS1) | (uint32_t)sm->digit;
     rank = sm->rank_in;
-    slow_pass<2>(ks, c, sh, seq, prefix, sm);
+    slow_pass<2>(ks, c, sh, sa, seq, prefix, sm);
     walk_from_top<1024>(sm, rank);
     prefix = (prefix << RADIX_BITS2) | (uint32_t)sm->digit;
     *rank_in = sm->rank_in;
@@ -184,17 +240,18 @@ __device__ __forceinline__ uint32_t slow_radix(const KeySource<SCORE>& ks, const
 
 // The `quota`-th entry (1-based) with key == key_thr in (segment ascending, position ascending) order:
 // result in sm->found_seg / sm->found_pos.  The caller guarantees that it exists.
-template <bool SCORE>
-__device__ __forceinline__ void slow_tie_walk(const KeySource<SCORE>& ks, const CacheView& c, const Shape& sh,
-                                              int seq, uint32_t key_thr, int64_t quota, ResolveShared* sm) {
+template <bool SCORE, bool STEP>
+__device__ __forceinline__ void slow_tie_walk(const KeySource<SCORE, STEP>& ks, const CacheView& c, const Shape& sh,
+                                              const StepArgs& sa, int seq, uint32_t key_thr, int64_t quota,
+                                              ResolveShared* sm) {
     const int tid = threadIdx.x;
     int64_t need = quota;
     for (int g = seq * sh.segs_per_seq; g < (seq + 1) * sh.segs_per_seq; ++g) {
-        int64_t start;
-        bool bad = false;
-        const int len = seg_checked_len(c, g, sh.nseg, &start, &bad);
+        bool bad = false, nocap = false;
+        const SegView v = seg_view<STEP>(c, g, sh.nseg, sa, &bad, &nocap);
+        const int len = v.len;
         int mine = 0;
-        for (int j = tid; j < len; j += FAST_THREADS) mine += key_of_score(ks.score_at(start + j)) == key_thr;
+        for (int j = tid; j < len; j += FAST_THREADS) mine += key_of_score(ks.score_at(g, v, j)) == key_thr;
         const int in_seg = block_sum<int32_t>(mine, sm->lds32);
         if (need > in_seg) {
             need -= in_seg;
@@ -204,12 +261,12 @@ __device__ __forceinline__ void slow_tie_walk(const KeySource<SCORE>& ks, const 
         int64_t running = 0;
         for (int base = 0; base < len; base += FAST_THREADS) {    // uniform trip count
             const int j = base + tid;
-            const int is_eq = j < len && key_of_score(ks.score_at(start + j)) == key_thr;
+            const int is_eq = j < len && key_of_score(ks.score_at(g, v, j)) == key_thr;
             int32_t tot;
             const int32_t ex = block_excl_scan<int32_t>(is_eq, sm->lds32, &tot);
             if (is_eq && running + ex == need - 1) {
                 sm->found_seg = g;
-                sm->found_pos = c.pos[start + j];
+                sm->found_pos = ks.pos_at(g, v, j);
             }
             running += tot;
             if (running >= need) break;                           // uniform: tot comes from LDS
@@ -228,25 +285,42 @@ template <typename T>
 __device__ __forceinline__ void st_dev(T* p, T v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
 // SCORE: stage 1 is computed here (and written to score_out); otherwise the scores are read from score_in.
+// STEP (implies SCORE): the decode step in one call.  Every block scores a segment's new tokens from the new-token
+// buffers; one more block per segment, behind the scanning blocks of the grid, writes their rows and metadata into
+// the source cache and the segment's part of the row mover's chunk table.  The last block of a sequence also leaves
+// what the compaction needs: survivors per segment, the destination's segment table, a destination offset per chunk
+// of 128 entries (flagged when the chunk loses nothing) and the mask bytes - of the chunks that lose entries only
+// when the evicted entries are on the candidate list (their indices pass through LDS), of every entry after the
+// single-block select or with more evictions than the LDS list holds.
 //
 // Cross-block traffic inside the kernel: the candidate lists, their counters, the lowest keys and the arrival
 // counters.  All of it is written with device-scope atomics or write-through stores whose acknowledgement the
 // writer waits for before it arrives, and read with device-scope loads - so no block needs a fence, which on this
 // chip means a write-back of a whole L2.  The scores written here are read by the NEXT kernel only; the
 // single-block select, which has to look at every entry, recomputes them from the call's inputs.
-template <bool SCORE>
+template <bool SCORE, bool STEP>
 __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const int32_t* __restrict__ now,
                                                             const float* score_in, float* score_out,
                                                             const int64_t* __restrict__ budget, Shape sh, Workspace ws,
                                                             int bps, int32_t* __restrict__ kept_out,
-                                                            uint32_t* __restrict__ thr_out) {
+                                                            uint32_t* __restrict__ thr_out, StepArgs sa) {
+    static_assert(!STEP || SCORE, "the one-call step computes the scores itself");
     __shared__ ResolveShared sm;
     __shared__ int s_last, s_ncand;
     __shared__ uint32_t s_base;
-    __shared__ uint32_t c_key[FAST_STAGE];                        // this block's candidates, before they go to the list
-    __shared__ int32_t c_pos[FAST_STAGE];
+    // this block's candidates, before they go to the list; the last block of a sequence reuses the space (STEP)
+    __shared__ int32_t s_pool[(STEP ? 6 : 2) * FAST_STAGE];
+    uint32_t* c_key = reinterpret_cast<uint32_t*>(s_pool);
+    int32_t* c_pos = s_pool + FAST_STAGE;
+    int32_t* c_idx = s_pool + (STEP ? 2 : 1) * FAST_STAGE;
+    __shared__ int s_ev[STEP ? STEP_MAX_SEGS : 1], s_off[STEP ? STEP_MAX_SEGS : 1];
+    __shared__ int s_seqcnt[STEP ? STEP_MAX_SEQS : 1];
+    static_assert(STEP_MAX_SEGS <= FAST_STAGE && STEP_MAX_SEGS <= FAST_THREADS && STEP_MAX_EVICT <= FAST_STAGE, "the step's tables reuse the staging space, one segment per thread");
     const int tid = threadIdx.x;
-    const int seg = blockIdx.x / bps, part = blockIdx.x % bps;
+    // STEP: behind the scanning blocks the grid has one block per segment that only writes the segment's tables
+    const bool tables_only = STEP && (int)blockIdx.x >= sh.nseg * bps;
+    const int seg = tables_only ? (int)blockIdx.x - sh.nseg * bps : (int)blockIdx.x / bps;
+    const int part = tables_only ? 0 : (int)blockIdx.x % bps;
     const int seq = seg / sh.segs_per_seq;
     // Device-scope atomics on one address are served one after the other (tens of nanoseconds each), so the
     // blocks of a sequence do not meet on one word: the list is kept in up to FAST_SUB sub-lists with a counter
@@ -257,51 +331,101 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
     const int sub = blk_in_seq % nsub;
     if (tid == 0) s_ncand = 0;
     __syncthreads();
-    int64_t start;
-    bool bad = false;
-    const int len = seg_checked_len(c, seg, sh.nseg, &start, &bad);
-    if (bad && tid == 0 && part == 0) atomicOr(ws.err, ERR_LAYOUT);
+    bool bad = false, nocap = false;
+    const SegView sv0 = seg_view<STEP>(c, seg, sh.nseg, sa, &bad, &nocap);
+    const int64_t start = sv0.start;
+    const int len = sv0.len;
+    if (tid == 0 && part == 0 && !tables_only && (bad || nocap)) atomicOr(ws.err, bad ? ERR_LAYOUT : ERR_CAP);
     const uint32_t hi = ws.fast_hi[seq];
     const uint32_t cap = (uint32_t)ws.fl_cap;
     const uint32_t subcap = cap / (uint32_t)nsub;                 // entries per sub-list
     uint32_t* lk = ws.fl_key + (size_t)seq * cap;
     int32_t* ls = ws.fl_seg + (size_t)seq * cap;
     int32_t* lp = ws.fl_pos + (size_t)seq * cap;
+    int32_t* li = ws.fl_idx + (size_t)seq * cap;
     uint32_t* sub_count = ws.fl_count + (size_t)seq * FAST_SUB;
     uint32_t* grp_min = ws.fast_min + (size_t)seq * FAST_SUB;
     uint32_t* done = ws.fast_done + (size_t)seq * (FAST_SUB + 1);
-    KeySource<SCORE> ks;
+    KeySource<SCORE, STEP> ks;
     ks.score_in = score_in;
     ks.lb = c.log_beta;
     ks.lt = c.log_tail;
     ks.pos = c.pos;
+    ks.lb_new = sa.lb_new;
+    ks.lt_new = sa.lt_new;
+    ks.pos_new = sa.pos_new;
+    ks.n_new = sa.n_new;
     ks.t1 = SCORE ? now[seq] + 1 : 0;
+
+    // STEP, the segment's tables-only block (it takes no part in the scan, so the sequence's last block never waits
+    // for this): the segment's new tokens enter the source cache, and the segment's part of the row mover's chunk
+    // table is written.  Both are read by the next kernel only.
+    if (tables_only) {
+        // ---- this segment's new tokens enter the source cache (rows: 16 bytes per thread; metadata)
+        const int cnt_new = sv0.len - sv0.len_old;
+        const int vpr = sh.head_dim / 8;
+        const uint4* kn = reinterpret_cast<const uint4*>(sa.k_new) + (int64_t)seg * sa.n_new * vpr;
+        const uint4* vn = reinterpret_cast<const uint4*>(sa.v_new) + (int64_t)seg * sa.n_new * vpr;
+        uint4* kd = reinterpret_cast<uint4*>(sa.src.k) + (start + sv0.len_old) * vpr;
+        uint4* vd = reinterpret_cast<uint4*>(sa.src.v) + (start + sv0.len_old) * vpr;
+        for (int i = tid; i < cnt_new * vpr; i += FAST_THREADS) {
+            kd[i] = kn[i];
+            vd[i] = vn[i];
+        }
+        for (int i = tid; i < cnt_new; i += FAST_THREADS) {
+            const int64_t e = start + sv0.len_old + i, ni = (int64_t)seg * sa.n_new + i;
+            sa.src.log_beta[e] = sa.lb_new[ni];
+            if (c.log_tail) sa.src.log_tail[e] = sa.lt_new[ni];
+            sa.src.pos[e] = sa.pos_new[ni];
+        }
+        // ---- and its part of the row mover's chunk table: the chunks of the segments before it are counted here
+        int before = 0;
+        for (int g = tid; g < seg; g += FAST_THREADS) {
+            bool b2 = false, n2 = false;
+            const SegView v = seg_view<STEP>(c, g, sh.nseg, sa, &b2, &n2);
+            before += (v.len + CMP_CHUNK - 1) / CMP_CHUNK;
+        }
+        before = block_sum<int32_t>(before, sm.lds32);
+        const int nch = (len + CMP_CHUNK - 1) / CMP_CHUNK;
+        for (int ch = tid; ch < nch; ch += FAST_THREADS) {
+            ChunkDesc d;
+            d.first = start + (int64_t)ch * CMP_CHUNK;
+            d.n = min(CMP_CHUNK, len - ch * CMP_CHUNK);
+            d.seg = seg;
+            ws.cmp_desc[before + ch] = d;
+        }
+        if (tid == 0) {
+            ws.cmp_chunk_prefix[seg] = before;
+            if (seg == sh.nseg - 1) ws.cmp_chunk_prefix[sh.nseg] = before + nch;
+            ws.step_len[seg] = len;
+        }
+        return;
+    }
 
     // ---- every entry of this block's share: score, and onto the list if its key is below the bound
     {
-        const int32_t* pos = c.pos + start;
         uint32_t mn = 0xFFFFFFFFu;
         // batches of FAST_BATCH entries per thread: all loads of a batch are issued before any of them is used
         for (int j0 = part * FAST_THREADS + tid; j0 < len; j0 += bps * FAST_THREADS * FAST_BATCH) {
             float sv[FAST_BATCH];
             int pv[FAST_BATCH];
             if (SCORE) {
-                const float* lb = c.log_beta + start;
-                const float* lt = c.log_tail ? c.log_tail + start : nullptr;
                 float lbv[FAST_BATCH], ltv[FAST_BATCH];
 #pragma unroll
                 for (int u = 0; u < FAST_BATCH; ++u) {
                     const int j = j0 + u * bps * FAST_THREADS;
                     const bool in = j < len;
-                    pv[u] = in ? pos[j] : 0;
-                    lbv[u] = in ? lb[j] : 0.f;
-                    ltv[u] = (in && lt) ? lt[j] : 0.f;
+                    const bool isnew = STEP && j >= sv0.len_old;
+                    const int64_t at = isnew ? (int64_t)seg * sa.n_new + (j - sv0.len_old) : start + j;
+                    pv[u] = in ? (isnew ? sa.pos_new : c.pos)[at] : 0;
+                    lbv[u] = in ? (isnew ? sa.lb_new : c.log_beta)[at] : 0.f;
+                    ltv[u] = (in && c.log_tail) ? (isnew ? sa.lt_new : c.log_tail)[at] : 0.f;
                 }
 #pragma unroll
                 for (int u = 0; u < FAST_BATCH; ++u) {
                     const int j = j0 + u * bps * FAST_THREADS;
                     const float dt = (float)(ks.t1 - pv[u]);
-                    sv[u] = lt ? __fmaf_rn(dt, lbv[u], ltv[u]) : __fmul_rn(dt, lbv[u]);
+                    sv[u] = c.log_tail ? __fmaf_rn(dt, lbv[u], ltv[u]) : __fmul_rn(dt, lbv[u]);
                     if (j < len) score_out[start + j] = sv[u];
                 }
             } else {
@@ -321,7 +445,8 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
                     const int slot = atomicAdd(&s_ncand, 1);
                     if (slot < FAST_STAGE) {
                         c_key[slot] = key;
-                        c_pos[slot] = SCORE ? pv[u] : pos[j];
+                        c_pos[slot] = SCORE ? pv[u] : c.pos[start + j];
+                        if (STEP) c_idx[slot] = j;
                     }
                 }
             }
@@ -343,6 +468,7 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
                     st_dev(&lk[at], c_key[i]);
                     st_dev(&ls[at], (int32_t)seg);
                     st_dev(&lp[at], c_pos[i]);
+                    if (STEP) st_dev(&li[at], c_idx[i]);
                 }
             }
         }
@@ -374,7 +500,7 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
         min_key = min(min_key, ld_dev(&grp_min[i]));
     }
     uint32_t key[FAST_ITEMS];
-    int sg[FAST_ITEMS], ps[FAST_ITEMS];
+    int sg[FAST_ITEMS], ps[FAST_ITEMS], ix[FAST_ITEMS];
     uint32_t slot_sub[FAST_ITEMS], slot_idx[FAST_ITEMS];
 #pragma unroll
     for (int u = 0; u < FAST_ITEMS; ++u) {
@@ -382,20 +508,53 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
         slot_sub[u] = i / subcap;
         slot_idx[u] = i - slot_sub[u] * subcap;
         key[u] = 0;
-        sg[u] = ps[u] = 0;
+        sg[u] = ps[u] = ix[u] = 0;
         if (i < cap && slot_sub[u] < (uint32_t)nsub) {
             key[u] = ld_dev(&lk[i]);
             sg[u] = ld_dev(&ls[i]);
             ps[u] = ld_dev(&lp[i]);
+            if (STEP) ix[u] = ld_dev(&li[i]);
         }
     }
     const int g0 = seq * sh.segs_per_seq;
     int64_t cnt = 0;
-    for (int g = g0 + tid; g < g0 + sh.segs_per_seq; g += FAST_THREADS) {
-        int64_t st;
-        bool b2 = false;
-        cnt += seg_checked_len(c, g, sh.nseg, &st, &b2);
-        kept_out[g] = 0;                                          // the mask kernel adds its counts
+    int64_t step_before = 0, step_total = 0;                      // STEP: destination entries before this sequence / of all sequences
+    int step_chunks_before = 0;                                   // STEP: chunks of the sequences before this one
+    if (STEP) {
+        // entries per sequence of the whole batch (the destination of a sequence starts behind all earlier ones)
+        for (int i = tid; i < sh.n_seq; i += FAST_THREADS) s_seqcnt[i] = 0;
+        __syncthreads();
+        int chunks_before = 0;
+        for (int g = tid; g < sh.nseg; g += FAST_THREADS) {
+            bool b2 = false, n2 = false;
+            const SegView v = seg_view<STEP>(c, g, sh.nseg, sa, &b2, &n2);
+            if (v.len) atomicAdd(&s_seqcnt[g / sh.segs_per_seq], v.len);
+            if (g < g0) chunks_before += (v.len + CMP_CHUNK - 1) / CMP_CHUNK;
+            if (g >= g0 && g < g0 + sh.segs_per_seq) kept_out[g] = 0;
+        }
+        step_chunks_before = block_sum<int32_t>(chunks_before, sm.lds32);
+        int64_t need = 0;
+        if (tid < sh.n_seq) {                                     // (n_seq <= FAST_THREADS here)
+            int64_t b = budget[tid];
+            if (b < 0) b = 0;
+            const int64_t n = s_seqcnt[tid];
+            need = (b < n ? b : n) + (int64_t)sa.reserve * sh.segs_per_seq;
+        }
+        int64_t tot;
+        const int64_t ex = block_excl_scan<int64_t>(need, sm.lds64, &tot);
+        if (tid == seq) sm.before = ex;
+        __syncthreads();
+        step_before = sm.before;
+        step_total = tot;
+        cnt = s_seqcnt[seq];
+        __syncthreads();
+    } else {
+        for (int g = g0 + tid; g < g0 + sh.segs_per_seq; g += FAST_THREADS) {
+            int64_t st;
+            bool b2 = false;
+            cnt += seg_checked_len(c, g, sh.nseg, &st, &b2);
+            kept_out[g] = 0;                                      // the mask kernel adds its counts
+        }
     }
     int64_t bud = budget[seq];
     if (bud < 0) bud = 0;
@@ -406,7 +565,7 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
         sub_overflow = sub_overflow || sub_n[i] > subcap;
         n_list += sub_n[i] > subcap ? subcap : sub_n[i];
     }
-    bool valid[FAST_ITEMS];
+    bool valid[FAST_ITEMS], listed[FAST_ITEMS];
     uint32_t lo = 0xFFFFFFFFu, hi_k = 0;
 #pragma unroll
     for (int u = 0; u < FAST_ITEMS; ++u) {
@@ -414,6 +573,7 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
 #pragma unroll
         for (int q = 0; q < FAST_SUB; ++q) n_here = slot_sub[u] == (uint32_t)q ? sub_n[q] : n_here;
         valid[u] = (uint32_t)tid + (uint32_t)u * FAST_THREADS < cap && slot_sub[u] < (uint32_t)nsub && slot_idx[u] < n_here;
+        listed[u] = valid[u];
         if (valid[u]) {
             lo = min(lo, key[u]);
             hi_k = max(hi_k, key[u]);
@@ -428,7 +588,7 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
         }
     }
     {   // entries of the sequence, lowest and highest listed key: one reduction
-        cnt = wave_sum(cnt);
+        if (!STEP) cnt = wave_sum(cnt);
 #pragma unroll
         for (int d = 32; d >= 1; d >>= 1) {
             lo = min(lo, (uint32_t)__shfl_xor((int)lo, d, 64));
@@ -440,9 +600,9 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
             sm.h[tid >> 6] = hi_k;
         }
         __syncthreads();
-        cnt = 0;
+        if (!STEP) cnt = 0;
         for (int i = 0; i < FAST_THREADS / 64; ++i) {
-            cnt += sm.lds64[i];
+            if (!STEP) cnt += sm.lds64[i];
             lo = min(lo, sm.red_u[i]);
             hi_k = max(hi_k, sm.h[i]);
         }
@@ -548,10 +708,10 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
             __syncthreads();
             int64_t rank_in;
             uint32_t ties;
-            const uint32_t key_thr = slow_radix(ks, c, sh, seq, want, &sm, &rank_in, &ties);
+            const uint32_t key_thr = slow_radix(ks, c, sh, sa, seq, want, &sm, &rank_in, &ties);
             out.key_thr = key_thr;
             if (rank_in < (int64_t)ties) {                        // only the first rank_in of the equal keys survive
-                slow_tie_walk(ks, c, sh, seq, key_thr, rank_in, &sm);
+                slow_tie_walk(ks, c, sh, sa, seq, key_thr, rank_in, &sm);
                 out.seg_thr = sm.found_seg;
                 out.pos_thr = sm.found_pos;
             }
@@ -560,7 +720,7 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
             const int64_t rank_b = want - above >= 1 ? want - above : 1;
             int64_t unused_r;
             uint32_t unused_t;
-            const uint32_t key_b = slow_radix(ks, c, sh, seq, rank_b, &sm, &unused_r, &unused_t);
+            const uint32_t key_b = slow_radix(ks, c, sh, sa, seq, rank_b, &sm, &unused_r, &unused_t);
             next_hi = key_b == 0xFFFFFFFFu ? key_b : key_b + 1u;
         }
     }
@@ -569,6 +729,178 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
         ws.fast_sel[seq] = out;
         if (thr_out) thr_out[seq] = out.mode == FSEL_NONE ? 0xFFFFFFFFu : out.key_thr;
         if (out.mode == FSEL_THRESHOLD) ws.fast_hi[seq] = next_hi;
+    }
+    if (!STEP) return;
+
+    // ---- STEP: what the row mover needs: survivors per segment, the destination's segment table, a destination
+    // offset per chunk of 128 entries (flagged when the chunk loses nothing) and the keep mask of the chunks that do
+    // lose entries.  Entry (g, position p, key) survives iff it is not behind the last retained entry `out`.
+    if (STEP) {
+        if (step_total > sa.dst.cap) {                            // every sequence's last block takes the same decision
+            if (tid == 0) atomicOr(ws.err, ERR_CAP);
+            return;
+        }
+        const int nsg = sh.segs_per_seq;
+        // The evicted entries are among the listed ones unless the single-block select ran; they go through LDS,
+        // so there must not be too many (nothing retained at all also takes the other route).
+        const bool sparse = out.mode == FSEL_ALL || (out.mode == FSEL_THRESHOLD && !used_fallback && k <= STEP_MAX_EVICT);
+        int* s_cb = s_pool;                                       // first chunk of the segment, counted inside the sequence
+        int* s_len = s_pool + FAST_STAGE;
+        int* s_evl = s_pool + 2 * FAST_STAGE;                     // evicted entries (index in their segment), segment by segment
+        int* s_start = s_pool + 3 * FAST_STAGE;                   // the segment's first entry in the source
+        int* s_lossy_sl = s_pool + 4 * FAST_STAGE;                // the chunks that lose entries: segment, chunk in it
+        int* s_lossy_ch = s_pool + 5 * FAST_STAGE;
+        uint32_t* s_fill = sm.h;                                  // fill counters of the scatter
+        uint32_t* s_dso = sm.h + STEP_MAX_SEGS;                   // the segment's destination, counted from the sequence's
+        if (sparse) {
+            __syncthreads();
+            if (tid < nsg) s_ev[tid] = 0;
+            s_fill[tid] = 0;
+            if (tid == 0) sm.gather_n = 0;
+            __syncthreads();
+            bool ev[FAST_ITEMS];
+#pragma unroll
+            for (int u = 0; u < FAST_ITEMS; ++u) {
+                ev[u] = out.mode == FSEL_THRESHOLD && listed[u] && evicted_before(key[u], sg[u], ps[u], out.key_thr, out.seg_thr, out.pos_thr);
+                if (ev[u]) atomicAdd(&s_ev[sg[u] - g0], 1);
+            }
+            __syncthreads();
+            int my_ev = 0, my_len = 0;                            // one segment per thread
+            int64_t my_start = 0;
+            if (tid < nsg) {
+                bool b2 = false, n2 = false;
+                const SegView v = seg_view<STEP>(c, g0 + tid, sh.nseg, sa, &b2, &n2);
+                my_len = v.len;
+                my_start = v.start;
+                my_ev = s_ev[tid];
+            }
+            int32_t etot, ctot;
+            const int32_t eex = block_excl_scan<int32_t>(my_ev, sm.lds32, &etot);
+            const int32_t cex = block_excl_scan<int32_t>((my_len + CMP_CHUNK - 1) / CMP_CHUNK, sm.lds32, &ctot);
+            int64_t ntot;
+            const int64_t nex = block_excl_scan<int64_t>(tid < nsg ? (int64_t)(my_len - my_ev) + sa.reserve : 0, sm.lds64, &ntot);
+            if (tid < nsg) {
+                const int g = g0 + tid;
+                s_off[tid] = eex;
+                s_cb[tid] = cex;
+                s_len[tid] = my_len;
+                s_start[tid] = (int)my_start;                     // (a context holds fewer than 2^31 entries)
+                s_dso[tid] = (uint32_t)nex;
+                kept_out[g] = my_len - my_ev;
+                sa.dst.seg_start[g] = step_before + nex;
+                sa.dst.seg_len[g] = my_len - my_ev;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < FAST_ITEMS; ++u) {
+                if (ev[u]) {
+                    const int sl = sg[u] - g0;
+                    s_evl[s_off[sl] + (int)atomicAdd(&s_fill[sl], 1u)] = ix[u];
+                }
+            }
+            __syncthreads();
+            // the chunks' destinations: neighbouring threads share a segment and take its chunks in turn
+            const int tps = nsg >= FAST_THREADS ? 1 : FAST_THREADS / nsg;
+            if (tid < nsg * tps) {
+                const int sl = tid / tps;
+                const int e0 = s_off[sl], ne = s_ev[sl], len_s = s_len[sl];
+                const int nch = (len_s + CMP_CHUNK - 1) / CMP_CHUNK;
+                int64_t* out_c = ws.cmp_chunk_dst + step_chunks_before + s_cb[sl];
+                const int64_t ds = step_before + (int64_t)s_dso[sl];
+                constexpr int EVR = 8;                            // the segment's first evicted entries stay in registers
+                int evr[EVR];
+#pragma unroll
+                for (int i = 0; i < EVR; ++i) evr[i] = i < ne ? s_evl[e0 + i] : 0x7fffffff;
+                for (int ch = tid % tps; ch < nch; ch += tps) {
+                    const int idx0 = ch * CMP_CHUNK;
+                    int before = 0, inside = 0;
+#pragma unroll
+                    for (int i = 0; i < EVR; ++i) {
+                        before += evr[i] < idx0;
+                        inside += evr[i] >= idx0 && evr[i] < idx0 + CMP_CHUNK;
+                    }
+                    for (int i = EVR; i < ne; ++i) {
+                        const int x = s_evl[e0 + i];
+                        before += x < idx0;
+                        inside += x >= idx0 && x < idx0 + CMP_CHUNK;
+                    }
+                    out_c[ch] = (ds + idx0 - before) | (inside == 0 ? CMP_DST_FULL : 0);
+                    if (inside) {
+                        const int slot = atomicAdd(&sm.gather_n, 1);   // (at most one per evicted entry)
+                        s_lossy_sl[slot] = sl;
+                        s_lossy_ch[slot] = ch;
+                    }
+                }
+            }
+            __syncthreads();
+            // the keep mask of the chunks that lose entries, 16 lanes per chunk and 8 entries per lane (the row mover
+            // writes the mask of the chunks that lose nothing)
+            const int nlossy = sm.gather_n;
+            for (int it = tid; it < nlossy * 16; it += FAST_THREADS) {
+                const int q = it >> 4, j0 = (it & 15) * 8;
+                const int sl = s_lossy_sl[q], idx0 = s_lossy_ch[q] * CMP_CHUNK;
+                const int e0 = s_off[sl], ne = s_ev[sl];
+                const int n = min(CMP_CHUNK, s_len[sl] - idx0);
+                unsigned gone = 0;                                // bit j: entry j0 + j of the chunk is evicted
+                for (int i = 0; i < ne; ++i) {
+                    const int x = s_evl[e0 + i] - idx0 - j0;
+                    if (x >= 0 && x < 8) gone |= 1u << x;
+                }
+                uint8_t* kp = sa.keep_out + (int64_t)s_start[sl] + idx0 + j0;
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (j0 + j < n) kp[j] = !((gone >> j) & 1u);
+            }
+        } else {
+            // after the single-block select (or with very many evictions) the evicted entries are not listed: one more
+            // pass over the sequence leaves the keep mask and, per chunk of 128 entries, where its survivors go
+            __syncthreads();
+            int64_t cursor = step_before;
+            int cb = step_chunks_before;
+            const int lane = lane_id(), wave = tid >> 6;
+            for (int g = g0; g < g0 + nsg; ++g) {
+                bool b2 = false, n2 = false;
+                const SegView v = seg_view<STEP>(c, g, sh.nseg, sa, &b2, &n2);
+                int64_t running = 0;
+                for (int t0 = 0; t0 < v.len; t0 += FAST_THREADS) {   // tiles of 8 chunks
+                    const int j = t0 + tid;
+                    bool kf = false;
+                    if (j < v.len) {
+                        if (out.mode == FSEL_THRESHOLD) {
+                            const uint32_t kk = key_of_score(ks.score_at(g, v, j));
+                            kf = !evicted_before(kk, g, kk == out.key_thr ? ks.pos_at(g, v, j) : 0, out.key_thr, out.seg_thr, out.pos_thr);
+                        } else {
+                            kf = out.mode == FSEL_ALL;
+                        }
+                        sa.keep_out[v.start + j] = kf;
+                    }
+                    const int wc = __popcll(__ballot(kf));
+                    __syncthreads();
+                    if (lane == 0) sm.h[wave] = wc;               // 16 wavefronts = 8 chunks of two
+                    __syncthreads();
+                    if (tid < FAST_THREADS / CMP_CHUNK) {
+                        const int chl = t0 / CMP_CHUNK + tid;     // chunk of the segment
+                        if (chl * CMP_CHUNK < v.len) {
+                            int64_t ex = 0;
+                            for (int i = 0; i < tid; ++i) ex += sm.h[2 * i] + sm.h[2 * i + 1];
+                            const int here = sm.h[2 * tid] + sm.h[2 * tid + 1];
+                            const int n = min(CMP_CHUNK, v.len - chl * CMP_CHUNK);
+                            ws.cmp_chunk_dst[cb + chl] = (cursor + running + ex) | (here == n ? CMP_DST_FULL : 0);
+                        }
+                    }
+                    int tile = 0;
+                    for (int i = 0; i < FAST_THREADS / 64; ++i) tile += sm.h[i];
+                    running += tile;
+                }
+                if (tid == 0) {
+                    kept_out[g] = (int32_t)running;
+                    sa.dst.seg_start[g] = cursor;
+                    sa.dst.seg_len[g] = (int32_t)running;
+                }
+                cursor += running + sa.reserve;
+                cb += (v.len + CMP_CHUNK - 1) / CMP_CHUNK;
+            }
+        }
     }
 }
 
@@ -632,9 +964,22 @@ kvtrim_status launch_score_select(kvtrim_ctx* ctx, const CacheView& c, const int
     bps = bps < 1 ? 1 : (bps > 64 ? 64 : bps);
     const dim3 grid((unsigned)(sh.nseg * bps)), block(FAST_THREADS);
     { ProfScope prof(ctx, K_FAST_SCAN, st);
-      hipLaunchKernelGGL(k_fast_scan<true>, grid, block, 0, st, c, now, (const float*)nullptr, score, budget, sh, ws, (int)bps, kept, thr); }
+      hipLaunchKernelGGL((k_fast_scan<true, false>), grid, block, 0, st, c, now, (const float*)nullptr, score, budget, sh, ws, (int)bps, kept, thr, StepArgs()); }
     { ProfScope prof(ctx, K_FAST_MASK, st);
       hipLaunchKernelGGL(k_fast_mask, grid, block, 0, st, c, (const float*)score, sh, ws, (int)bps, keep, kept); }
+    KVTRIM_HIP(ctx, hipGetLastError());
+    return KVTRIM_OK;
+}
+
+// The scoring kernel of the one-call decode step (the caller has checked that the step fits its limits).
+kvtrim_status launch_step_scan(kvtrim_ctx* ctx, const CacheView& c, const int32_t* now, const int64_t* budget, float* score,
+                               int32_t* kept, uint32_t* thr, const StepArgs& sa, hipStream_t st) {
+    const Shape& sh = ctx->shape;
+    int64_t bps = c.cap / ((int64_t)sh.nseg * FAST_ENTRIES_PER_BLOCK);
+    bps = bps < 1 ? 1 : (bps > 64 ? 64 : bps);
+    ProfScope prof(ctx, K_FAST_SCAN, st);
+    hipLaunchKernelGGL((k_fast_scan<true, true>), dim3((unsigned)(sh.nseg * bps + sh.nseg)), dim3(FAST_THREADS), 0, st, c, now,
+                       (const float*)nullptr, score, budget, sh, ctx->ws, (int)bps, kept, thr, sa);
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;
 }

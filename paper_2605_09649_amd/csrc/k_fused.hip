@@ -85,12 +85,18 @@ __device__ __forceinline__ float row16_sum(float x) {
 // whose destination lies in an earlier chunk's range - which another block may still be reading - go to the same
 // index of `stage` instead, and k_cmp_unstage puts them in place after this kernel has ended.  Rows that do not move
 // are not written at all.
-template <int D, int G, bool INPLACE>
-__global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const uint8_t* __restrict__ keep,
+// STEP (the one-call decode step, kvtrim_decode_step; out of place only): the tables come from the step's scoring
+// kernel instead of a compaction scan - the same per-chunk descriptors and destination offsets, and the keep mask
+// only where a chunk loses entries.  The kernel then also writes the keep mask of the chunks that lose nothing
+// (`keep` is the caller's output array) and commits the source segment's new length (step_seg_len = the source
+// cache's seg_len array; the new token was appended by the scoring kernel).
+template <int D, int G, bool INPLACE, bool STEP = false>
+__global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const uint8_t* keep,
                                                           CacheViewMut dst, CacheViewMut stage,
                                                           const uint16_t* __restrict__ q,
                                                           Shape sh, Workspace ws, float scale_log2,
-                                                          int layer_begin, int layer_end) {
+                                                          int layer_begin, int layer_end, int32_t* step_seg_len = nullptr) {
+    static_assert(!(STEP && INPLACE), "the one-call step compacts out of place");
     typedef Row<D> R;
     typedef typename R::vec vec;
     constexpr int E = R::E;
@@ -127,6 +133,7 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
             if (src.log_tail) md_lt = src.log_tail[sbase + tid];
             md_pos = src.pos[sbase + tid];
         }
+        if (STEP && tid < cd.n) const_cast<uint8_t*>(keep)[sbase + tid] = 1;   // (chunks that lose entries have their mask already)
     } else {
         int rank = 0;
         bool flag = false;
@@ -165,6 +172,7 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
     const int seq = seg / sh.segs_per_seq, lh = seg % sh.segs_per_seq;
     const int layer = lh / sh.n_kv_heads, head = lh % sh.n_kv_heads;
     const bool attend = layer >= layer_begin && layer < layer_end;   // uniform over the block
+    if (STEP && tid == 0 && sbase == src.seg_start[seg]) step_seg_len[seg] = ws.step_len[seg];   // the segment's first chunk
     const int sub = lane >> 4, col = lane & 15;
     const int r0 = wave * CMP_WAVE_ROWS;                          // this wavefront's rows of the survivor list
     const bool has_rows = r0 < cnt;                               // uniform over the wavefront
@@ -610,6 +618,47 @@ kvtrim_status launch_compact_attn_inplace(kvtrim_ctx* ctx, const CacheViewMut& c
             hipLaunchKernelGGL(k_cmp_unstage<64>, grid, dim3(UNS_THREADS), 0, st, c, stage, kept, sh, ws, run_chunks);
     }
     return launch_combine(ctx, loop_shaped ? ws.att_chunk_prefix : ws.cmp_chunk_prefix, layer_begin, layer_end, out, lse, st);
+}
+
+kvtrim_status launch_decode_step(kvtrim_ctx* ctx, const CacheViewMut& srcm, const StepArgs& sa, const int32_t* now,
+                                 const int64_t* budget, float* score, int32_t* kept, uint32_t* thr, const uint16_t* q,
+                                 int32_t layer_begin, int32_t layer_end, float scale, float* out, float* lse,
+                                 int64_t evict_hint, hipStream_t st) {
+    const Shape& sh = ctx->shape;
+    const Workspace& ws = ctx->ws;
+    CacheView src;
+    src.k = srcm.k; src.v = srcm.v; src.log_beta = srcm.log_beta; src.pos = srcm.pos;
+    src.seg_start = srcm.seg_start; src.seg_len = srcm.seg_len; src.cap = srcm.cap; src.log_tail = srcm.log_tail;
+    const int64_t max_chunks = src.cap / CMP_CHUNK + sh.nseg;
+    const bool alu_fits = sh.head_dim == 128 ? sh.group <= FUSED_ONE_SHOT_MAX_G_128 : sh.group <= FUSED_ONE_SHOT_MAX_G_64;
+    // Three kernels (score + resolve, move + attend, merge) when this is a decode step the candidate list can carry
+    // and the one-shot fused kernel serves the shape; otherwise the calls it stands for, one after the other.
+    const bool three = evict_hint > 0 && 8 * (evict_hint + 1) <= (int64_t)ws.fl_cap && alu_fits &&
+                       sh.segs_per_seq <= STEP_MAX_SEGS && sh.n_seq <= STEP_MAX_SEQS && sa.n_new <= STEP_MAX_NEW &&
+                       max_chunks <= ws.max_att_chunks && max_chunks <= ws.max_cmp_chunks;
+    if (!three) {
+        kvtrim_status rc = launch_append(ctx, srcm, sa.k_new, sa.v_new, sa.lb_new, sa.lt_new, sa.pos_new, sa.n_new, true, nullptr, st);
+        if (rc != KVTRIM_OK) return rc;
+        rc = launch_score_select(ctx, src, now, budget, score, sa.keep_out, kept, thr, evict_hint, st);
+        if (rc != KVTRIM_OK) return rc;
+        return launch_compact_attn(ctx, src, sa.keep_out, kept, sa.dst, sa.reserve, q, layer_begin, layer_end, scale, out, lse, st);
+    }
+    kvtrim_status rc = launch_step_scan(ctx, src, now, budget, score, kept, thr, sa, st);
+    if (rc != KVTRIM_OK) return rc;
+    {
+        ProfScope prof(ctx, K_CMP_ATTN, st);
+        const float scale_log2 = scale * 1.4426950408889634f;
+        const dim3 grid((unsigned)max_chunks), block(FUS_THREADS);
+        switch (sh.head_dim * 16 + sh.group) {
+#define KVTRIM_CASE(d, g) \
+    case d * 16 + g: hipLaunchKernelGGL((k_cmp_attn<d, g, false, true>), grid, block, 0, st, src, (const uint8_t*)sa.keep_out, sa.dst, sa.dst, q, sh, ws, scale_log2, layer_begin, layer_end, srcm.seg_len); break;
+            KVTRIM_CASE(128, 1) KVTRIM_CASE(128, 2) KVTRIM_CASE(128, 3) KVTRIM_CASE(128, 4) KVTRIM_CASE(128, 5)
+            KVTRIM_CASE(64, 1) KVTRIM_CASE(64, 2) KVTRIM_CASE(64, 3) KVTRIM_CASE(64, 4)
+#undef KVTRIM_CASE
+            default: return KVTRIM_EINVAL;
+        }
+    }
+    return launch_combine(ctx, ws.cmp_chunk_prefix, layer_begin, layer_end, out, lse, st);
 }
 
 }  // namespace kvtrim

@@ -33,7 +33,7 @@ static bool config_ok(const kvtrim_config* c) {
 }
 
 struct Layout {
-    size_t off[32];
+    size_t off[40];
     int32_t fl_cap;
     size_t total;
     int64_t max_sel_chunks, max_cmp_chunks, max_att_chunks;
@@ -98,6 +98,8 @@ static Layout layout_of(const kvtrim_config* c, bool select_only) {
     l.off[29] = bump(cur, (size_t)c->n_seq * l.fl_cap * sizeof(uint32_t));     // fl_key
     l.off[30] = bump(cur, (size_t)c->n_seq * l.fl_cap * sizeof(int32_t));      // fl_seg
     l.off[31] = bump(cur, (size_t)c->n_seq * l.fl_cap * sizeof(int32_t));      // fl_pos
+    l.off[32] = bump(cur, (size_t)c->n_seq * l.fl_cap * sizeof(int32_t));      // fl_idx
+    l.off[33] = bump(cur, seg_tables * (size_t)nseg * sizeof(int32_t));        // step_len
     l.total = (cur + 255) & ~(size_t)255;
     return l;
 }
@@ -137,6 +139,8 @@ static void bind(const Layout& l, char* b, Workspace& w) {
     w.fl_key = (uint32_t*)(b + l.off[29]);
     w.fl_seg = (int32_t*)(b + l.off[30]);
     w.fl_pos = (int32_t*)(b + l.off[31]);
+    w.fl_idx = (int32_t*)(b + l.off[32]);
+    w.step_len = (int32_t*)(b + l.off[33]);
     w.fl_cap = l.fl_cap;
     w.max_sel_chunks = l.max_sel_chunks;
     w.max_cmp_chunks = l.max_cmp_chunks;
@@ -504,6 +508,48 @@ kvtrim_status kvtrim_append(kvtrim_ctx* ctx, kvtrim_cache* c, const void* k_new,
         return invalid(ctx, "log_tail_new is required exactly when the cache carries log_tail");
     return launch_append(ctx, view_mut_of(c), (const uint16_t*)k_new, (const uint16_t*)v_new, log_beta_new,
                          log_tail_new, pos_new, n_new, true, nullptr, (hipStream_t)hip_stream);
+}
+
+kvtrim_status kvtrim_decode_step(kvtrim_ctx* ctx, kvtrim_cache* src, const void* k_new, const void* v_new,
+                                 const float* log_beta_new, const float* log_tail_new, const int32_t* pos_new,
+                                 int32_t n_new, const int32_t* now, const int64_t* budget, float* score_out,
+                                 uint8_t* keep_out, int32_t* kept_out, uint32_t* thr_key_out, kvtrim_cache* dst,
+                                 int32_t reserve, const void* q, int32_t layer_begin, int32_t layer_end,
+                                 float softmax_scale, float* out, float* lse, int64_t evict_hint, void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    if (const char* p = cache_problem(ctx, src, true)) return invalid(ctx, p);
+    if (const char* p = cache_problem(ctx, dst, true)) return invalid(ctx, p);
+    if (!k_new || !v_new || !log_beta_new || !pos_new) return invalid(ctx, "a new-token pointer is NULL");
+    if ((((uintptr_t)k_new) | ((uintptr_t)v_new)) & 15) return invalid(ctx, "k_new / v_new not 16-byte aligned");
+    if (n_new < 1) return invalid(ctx, "n_new < 1");
+    if ((src->log_tail == nullptr) != (log_tail_new == nullptr))
+        return invalid(ctx, "log_tail_new is required exactly when the cache carries log_tail");
+    if (!now || !budget || !score_out || !keep_out || !kept_out)
+        return invalid(ctx, "now / budget / score_out / keep_out / kept_out is NULL");
+    if (reserve < 0) return invalid(ctx, "reserve < 0");
+    if (src->k == dst->k || src->v == dst->v || src->log_beta == dst->log_beta || src->pos == dst->pos ||
+        src->seg_start == dst->seg_start || src->seg_len == dst->seg_len)
+        return invalid(ctx, "src and dst share a buffer");
+    if ((src->log_tail == nullptr) != (dst->log_tail == nullptr) || (src->log_tail && src->log_tail == dst->log_tail))
+        return invalid(ctx, "log_tail must be set in both caches or in neither, and not shared");
+    if (!q || !out) return invalid(ctx, "q / out is NULL");
+    if (((uintptr_t)q) & 15) return invalid(ctx, "q not 16-byte aligned");
+    if (layer_begin < 0 || layer_end > ctx->cfg.n_layers || layer_begin >= layer_end)
+        return invalid(ctx, "empty or out-of-range layer range");
+    if (!(softmax_scale == softmax_scale)) return invalid(ctx, "softmax_scale is NaN");
+    StepArgs sa;
+    sa.k_new = (const uint16_t*)k_new;
+    sa.v_new = (const uint16_t*)v_new;
+    sa.lb_new = log_beta_new;
+    sa.lt_new = log_tail_new;
+    sa.pos_new = pos_new;
+    sa.n_new = n_new;
+    sa.src = view_mut_of(src);
+    sa.dst = view_mut_of(dst);
+    sa.reserve = reserve;
+    sa.keep_out = keep_out;
+    return launch_decode_step(ctx, sa.src, sa, now, budget, score_out, kept_out, thr_key_out, (const uint16_t*)q, layer_begin,
+                              layer_end, softmax_scale, out, lse, evict_hint, (hipStream_t)hip_stream);
 }
 
 kvtrim_status kvtrim_append_compact(kvtrim_ctx* ctx, kvtrim_cache* src, const void* k_new, const void* v_new,

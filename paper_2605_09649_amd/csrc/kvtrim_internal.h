@@ -83,6 +83,26 @@ struct FastSel {
     int32_t pos_thr;
 };
 
+// The decode step in one call (kvtrim_decode_step): the tokens that enter the cache in this step (laid out as kvtrim_append takes them;
+// their rows also go into the source cache) and where the compaction goes.
+struct StepArgs {
+    const uint16_t* k_new;
+    const uint16_t* v_new;
+    const float* lb_new;
+    const float* lt_new;
+    const int32_t* pos_new;
+    int n_new;
+    CacheViewMut src;            // the source cache again, writable
+    CacheViewMut dst;
+    int reserve;
+    uint8_t* keep_out;
+};
+
+constexpr int STEP_MAX_SEGS = 1024;  // segments per sequence the one-call decode step handles
+constexpr int STEP_MAX_EVICT = 1024; // evictions per sequence it lists (more: the keep mask and per-chunk offsets are written by one block)
+constexpr int STEP_MAX_SEQS = 1024;  // sequences it handles
+constexpr int STEP_MAX_NEW = 16;     // new tokens per segment and step
+
 // One chunk of a segment: entries [first, first + n) of the flat arrays.
 struct ChunkDesc {
     int64_t first;
@@ -138,7 +158,10 @@ struct Workspace {
     uint32_t* fl_key;            // [n_seq][fl_cap] in up to 16 sub-lists of fl_cap / n_sub entries
     int32_t* fl_seg;             // [n_seq][fl_cap]
     int32_t* fl_pos;             // [n_seq][fl_cap]
+    int32_t* fl_idx;             // [n_seq][fl_cap] index of the entry in its segment (one-call decode step)
     int32_t fl_cap;
+    // one-call decode step
+    int32_t* step_len;           // [nseg] segment lengths with the step's new tokens
     int64_t max_sel_chunks, max_cmp_chunks, max_att_chunks;
 };
 
@@ -184,6 +207,13 @@ kvtrim_status launch_select(kvtrim_ctx*, const CacheView&, const float* score, c
 // carried bound, resolved by the last block of every sequence, and the mask pass.
 kvtrim_status launch_score_select(kvtrim_ctx*, const CacheView&, const int32_t* now, const int64_t* budget, float* score,
                                   uint8_t* keep, int32_t* kept, uint32_t* thr, int64_t evict_hint, hipStream_t);
+kvtrim_status launch_step_scan(kvtrim_ctx*, const CacheView&, const int32_t* now, const int64_t* budget, float* score,
+                               int32_t* kept, uint32_t* thr, const StepArgs& sa, hipStream_t);
+// The decode step in one call: append, stages 1 + 2, stages 3 + 4 (three kernels when the step is a decode step).
+kvtrim_status launch_decode_step(kvtrim_ctx*, const CacheViewMut& src, const StepArgs& sa, const int32_t* now,
+                                 const int64_t* budget, float* score, int32_t* kept, uint32_t* thr, const uint16_t* q,
+                                 int32_t layer_begin, int32_t layer_end, float scale, float* out, float* lse,
+                                 int64_t evict_hint, hipStream_t);
 kvtrim_status launch_score_select_general(kvtrim_ctx*, const CacheView&, const int32_t* now, const int64_t* budget,
                                           float* score, uint8_t* keep, int32_t* kept, uint32_t* thr, hipStream_t);
 kvtrim_status launch_compact(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const int32_t* kept,

@@ -44,9 +44,9 @@ def attn_error(out_gpu, out_ref):
 class GpuLoop:
     """Device-side state of the decode loop: ping-pong caches and the per-step scratch outputs."""
 
-    def __init__(self, w, cache_dict, budget, reserve, extra_entries, device, fused=False, hint=None):
+    def __init__(self, w, cache_dict, budget, reserve, extra_entries, device, fused=False, hint=None, one_call=False):
         self.w, self.device, self.reserve, self.fused, self.hint = w, device, reserve, fused, hint
-        self.calls = 0
+        self.calls, self.one_call = 0, one_call
         self.src = kv.Cache.from_dict(cache_dict, device)
         total = int(cache_dict["seg_len"].sum())
         dst_cap = min(int(sum(budget)), total + extra_entries) + w.nseg * reserve + 8
@@ -67,6 +67,15 @@ class GpuLoop:
 
     def step(self, inp, now_dev, pos_new_dev):
         ctx = self.ctx
+        if self.one_call:                          # the whole step through kvtrim_decode_step
+            hint = self.hint[min(self.calls, len(self.hint) - 1)] if isinstance(self.hint, (list, tuple)) else (self.hint or 0)
+            self.calls += 1
+            dst = self.spare[self.flip]
+            kv.kvtrim_decode_step(ctx, self.src, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos_new_dev, 1, now_dev,
+                                  self.budget, self.score, self.keep, self.kept, dst, self.reserve, inp["q"], 0, self.w.n_layers,
+                                  self.scale, self.out, self.lse, thr_key_out=self.thr, log_tail_new=inp.get("log_tail_new"),
+                                  evict_hint=hint)
+            return dst
         kv.kvtrim_append(ctx, self.src, inp["k_new"], inp["v_new"], inp["log_beta_new"], pos_new_dev, 1,
                          log_tail_new=inp.get("log_tail_new"))
         if self.hint is None:
@@ -94,7 +103,7 @@ class GpuLoop:
 
 
 def run_steps_both(w, steps, budget, device="cuda:0", reserve=1, cache_dict=None, now0=None, fused=False, horizon=1,
-                   hint=None, budget_per_step=None):
+                   hint=None, budget_per_step=None, one_call=False):
     """Returns one dict per step with the comparison results.  hint: None = kvtrim_score + kvtrim_select_global,
     otherwise kvtrim_score_select with that evict_hint.  budget_per_step: a list of budgets, one per step."""
     if cache_dict is None:
@@ -102,7 +111,7 @@ def run_steps_both(w, steps, budget, device="cuda:0", reserve=1, cache_dict=None
         now0 = [t - 1 for t in w.prefill]
     cache_dict = ki.with_horizon(cache_dict, horizon)
     hc = host_cache(w, cache_dict)
-    gpu = GpuLoop(w, cache_dict, budget, reserve, steps * w.nseg, device, fused=fused, hint=hint)
+    gpu = GpuLoop(w, cache_dict, budget, reserve, steps * w.nseg, device, fused=fused, hint=hint, one_call=one_call)
     budget_np = np.array(list(budget), np.int64)
     now = np.array(now0, np.int32)
     per_seq = w.n_layers * w.n_kv_heads
@@ -140,6 +149,9 @@ def run_steps_both(w, steps, budget, device="cuda:0", reserve=1, cache_dict=None
             "attn_err": attn_error(gpu.out.cpu().numpy(), out_ref),
             "kept_total": int(kept_ref.sum()),
         }
+        if one_call:                               # the source cache afterwards: the new token is in it
+            res["src_equal"] = bool(compare_cache_contents(device_cache_to_host(w, gpu.src), hc)) and \
+                bool(np.array_equal(gpu.src.seg_len.cpu().numpy(), hc.seg_len))
         if hint is not None:
             res["path_counts"] = kv.kvtrim_select_path_counts(gpu.ctx)
         fin = np.isfinite(lse_ref)

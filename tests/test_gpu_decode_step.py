@@ -1,0 +1,193 @@
+"""GPU parity of kvtrim_decode_step (append + stages 1-4 in one call, three kernels for a decode step) against the
+oracle's five operations: scores, mask, counts, threshold, the compacted cache, the source cache with the new token,
+attention - through whole decode loops, in its list form (few evictions), its mask form (after the single-block
+select: ties, budget drops) and the shapes that make it run the separate calls."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import kvtrim_inputs as ki
+import oracle
+import paper_2605_09649_amd as kv
+from harness import attn_error, compare_caches, device_cache_to_host, run_steps_both
+from helpers import bf16_bits, host_cache
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+ATTN_TOL = 5e-3
+
+
+def check(results, what=""):
+    for i, r in enumerate(results):
+        assert r["status"] == 0, (what, i, r)
+        assert r["score_equal"], (what, i, "score bits differ")
+        assert r["keep_equal"], (what, i, "selection differs")
+        assert r["cache_equal"], (what, i, "compacted cache differs")
+        assert r["src_equal"], (what, i, "source cache differs after the step")
+        assert r["attn_err"] <= ATTN_TOL and r["lse_err"] <= 2e-3 and r["lse_inf_equal"], (what, i, r)
+
+
+def wl(S, L, H, G, D):
+    return ki.Workload("t", 0, S, L, H, G * H, D, (0,) * S, (0,) * S, 1, 3.0, 1.5)
+
+
+def test_tiny_workload_full_loop():
+    w = ki.workload("tiny")
+    res = run_steps_both(w, steps=16, budget=w.budget, device=DEV, one_call=True, hint=[0, 16])
+    check(res)
+    assert res[-1]["path_counts"] == (15, 0)                      # every decode step resolved from its candidate list
+
+
+@pytest.mark.parametrize("name,prefill,steps", [("llama", 700, 5), ("long", 900, 5), ("vlm", 640, 4), ("multiturn", 600, 4)])
+def test_scaled_down_workloads(name, prefill, steps):
+    w = ki.workload(name, prefill=prefill)                        # vlm: 7 query heads per KV head -> the separate calls
+    check(run_steps_both(w, steps=steps, budget=w.budget, device=DEV, one_call=True, hint=[0, w.n_layers * w.n_kv_heads]), name)
+
+
+@pytest.mark.parametrize("horizon", [2, 0])
+def test_lookahead_horizon(horizon):
+    w = ki.workload("tiny", prefill=500)
+    check(run_steps_both(w, steps=5, budget=w.budget, device=DEV, one_call=True, hint=[0, 16], horizon=horizon), horizon)
+
+
+@pytest.mark.parametrize("S,L,H,G,D", [(1, 2, 2, 1, 128), (2, 2, 1, 5, 128), (3, 1, 2, 3, 64), (1, 2, 1, 4, 128), (1, 1, 3, 4, 64),
+                                       (1, 1, 2, 7, 128)])
+def test_ragged_segments_spanning_several_blocks(S, L, H, G, D):
+    w = wl(S, L, H, G, D)
+    rng = np.random.default_rng(S * 1000 + G * 10 + D)
+    seg_len = rng.integers(0, 20000, w.nseg)                      # more than one 8192-entry share per segment
+    seg_len[rng.integers(0, w.nseg)] = 0
+    seg_len[rng.integers(0, w.nseg)] = 8192 * 2 + 1
+    c, now = ki.ragged_cache(w, seg_len, reserve=1, salt=G)
+    per_seq = [int(seg_len[s * L * H:(s + 1) * L * H].sum()) for s in range(S)]
+    budget = [max(1, n // 3) for n in per_seq]
+    check(run_steps_both(w, steps=5, budget=budget, device=DEV, cache_dict=c, now0=now.numpy(), one_call=True, hint=[0, L * H]))
+
+
+def test_budget_changes_nothing_to_evict_and_nothing_to_keep():
+    w = wl(2, 2, 2, 2, 64)
+    rng = np.random.default_rng(8)
+    seg_len = rng.integers(50, 900, w.nseg)
+    c, now = ki.ragged_cache(w, seg_len, reserve=1, salt=3)
+    n0 = [int(seg_len[:4].sum()), int(seg_len[4:].sum())]
+    steps = [[10 ** 9, 10 ** 9], [n0[0] + 8, n0[1]], [n0[0] // 3, n0[1] - 5], [n0[0] // 3, n0[1] - 5], [n0[0] // 3, n0[1] - 5],
+             [n0[0] // 3 + 2, n0[1] - 9], [0, n0[1] - 9], [5, 0]]
+    res = run_steps_both(w, steps=len(steps), budget=[10 ** 9, 10 ** 9], device=DEV, cache_dict=c, now0=now.numpy(), one_call=True,
+                         hint=8, budget_per_step=steps)
+    check(res)
+
+
+@pytest.mark.parametrize("levels", [1, 2, 5])
+def test_ties_at_the_threshold_every_step_take_the_mask_form(levels):
+    w = wl(2, 2, 3, 2, 64)
+    rng = np.random.default_rng(40 + levels)
+    seg_len = rng.integers(100, 1500, w.nseg)
+    c, now = ki.ragged_cache(w, seg_len, reserve=1, salt=levels, pos_stride_max=1)
+    g = torch.Generator().manual_seed(levels)
+    c["log_beta"] = -(torch.randint(0, levels, c["log_beta"].shape, generator=g).to(torch.float32) + 1.0) * 0.125
+    budget = [int(seg_len[:6].sum()) // 2, int(seg_len[6:].sum()) - 7]
+    for hint in (6, 200):
+        clone = {k: (v.clone() if torch.is_tensor(v) else v) for k, v in c.items()}
+        check(run_steps_both(w, steps=5, budget=budget, device=DEV, cache_dict=clone, now0=now.numpy(), one_call=True, hint=hint),
+              (levels, hint))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_configuration(seed):
+    from test_gpu_random_sweep import random_case
+    w, c, now, budgets = random_case(seed)
+    for hint in (1 + seed % 7, 300):
+        clone = {k: (v.clone() if torch.is_tensor(v) else v) for k, v in c.items()}
+        res = run_steps_both(w, steps=len(budgets), budget=[max(b[s] for b in budgets) for s in range(w.n_seq)], device=DEV,
+                             cache_dict=clone, now0=now.numpy(), one_call=True, hint=hint, budget_per_step=budgets)
+        check(res, (seed, hint))
+
+
+@pytest.mark.parametrize("S,L,H", [(600, 1, 2), (1100, 1, 1)])
+def test_many_short_sequences(S, L, H):
+    rng = np.random.default_rng(77 + S)
+    w = ki.Workload("m", 0, S, L, H, 2 * H, 64, (0,) * S, (0,) * S, 1, 3.0, 1.5)
+    seg_len = rng.integers(0, 41, w.nseg)
+    seg_len[rng.random(w.nseg) < 0.1] = 0
+    c, now = ki.ragged_cache(w, seg_len, reserve=1, salt=S, pos_stride_max=2)
+    per_seq = [int(seg_len[s * L * H:(s + 1) * L * H].sum()) for s in range(S)]
+    budget = [0 if rng.random() < 0.05 else int(rng.integers(1, max(2, n + 3))) for n in per_seq]
+    check(run_steps_both(w, steps=3, budget=budget, device=DEV, cache_dict=c, now0=now.numpy(), one_call=True, hint=2), S)
+
+
+def _one_step(w, c, now, budget, reserve, hint, layer_range=None, dst_cap=None, n_new=1, pad=None):
+    """One call on a fresh context; returns the GPU's results and the oracle's."""
+    L = w.n_layers
+    lb, le = layer_range or (0, L)
+    per_seq = L * w.n_kv_heads
+    hc = host_cache(w, c)
+    src = kv.Cache.from_dict(c, DEV)
+    total = int(hc.seg_len.sum()) + n_new * w.nseg
+    cap2 = dst_cap or (total + w.nseg * reserve + 8)
+    dst = kv.Cache.empty(w.nseg, w.head_dim, cap2, DEV)
+    ctx = kv.Context(w.n_seq, L, w.n_kv_heads, w.n_q_heads, w.head_dim, max(src.cap, cap2))
+    inp = ki.chunk_inputs(w, n_new, "cpu", 5)
+    qg = torch.Generator().manual_seed(9)
+    q = torch.randn(w.n_seq, L, w.n_q_heads, w.head_dim, generator=qg).to(torch.bfloat16)
+    now_np = now.numpy() + n_new
+    pos_new = np.zeros((w.nseg, n_new), np.int32)
+    for s in range(w.n_seq):
+        pos_new[s * per_seq:(s + 1) * per_seq] = now.numpy()[s] + 1 + np.arange(n_new)
+    if pad is not None:                                           # segments that take fewer tokens: padding rows
+        for g, take in pad.items():
+            pos_new[g, take:] = -1
+    n = max(src.cap, cap2)
+    score = torch.zeros(n, dtype=torch.float32, device=DEV)
+    keep = torch.zeros(n, dtype=torch.uint8, device=DEV)
+    kept = torch.zeros(w.nseg, dtype=torch.int32, device=DEV)
+    thr = torch.zeros(w.n_seq, dtype=torch.int32, device=DEV)
+    out = torch.full((w.n_seq, L, w.n_q_heads, w.head_dim), 7.0, dtype=torch.float32, device=DEV)
+    lse = torch.full((w.n_seq, L, w.n_q_heads), 7.0, dtype=torch.float32, device=DEV)
+    scale = 1.0 / math.sqrt(w.head_dim)
+    bud = np.array(budget, np.int64)
+    kv.kvtrim_decode_step(ctx, src, inp["k_new"].to(DEV), inp["v_new"].to(DEV), inp["log_beta_new"].to(DEV),
+                          torch.from_numpy(pos_new).to(DEV), n_new, torch.from_numpy(now_np).to(DEV), torch.from_numpy(bud).to(DEV),
+                          score, keep, kept, dst, reserve, q.to(DEV), lb, le, scale, out, lse, thr_key_out=thr, evict_hint=hint)
+    status = kv.kvtrim_poll_error(ctx)
+    ref = None
+    try:
+        oracle.append(hc, bf16_bits(inp["k_new"]), bf16_bits(inp["v_new"]), inp["log_beta_new"].numpy(), pos_new)
+        s_ref = oracle.score(hc, now_np)
+        keep_ref, kept_ref, thr_ref = oracle.select(hc, s_ref, bud)
+        hc2 = oracle.compact(hc, keep_ref, cap2, reserve)
+        out_ref, lse_ref = oracle.attend(hc2, bf16_bits(q), scale, lb, le)
+        ref = dict(kept=kept_ref, thr=thr_ref, cache=hc2, out=out_ref, lse=lse_ref)
+    except OverflowError:
+        pass
+    return dict(status=status, kept=kept, thr=thr, dst=dst, out=out, lse=lse, src=src, ctx=ctx), ref
+
+
+def test_attention_of_a_layer_range_only_and_several_new_tokens_per_segment():
+    w = wl(1, 4, 2, 2, 128)
+    rng = np.random.default_rng(2)
+    seg_len = rng.integers(200, 3000, w.nseg)
+    c, now = ki.ragged_cache(w, seg_len, reserve=3, salt=2)
+    total = int(seg_len.sum())
+    # three new tokens per segment, two segments bring fewer (padding rows); a first call on a context: the mask form
+    g, ref = _one_step(w, c, now, [total - 10], 3, hint=24, layer_range=(1, 3), n_new=3, pad={2: 1, 5: 0})
+    assert g["status"] == 0
+    assert np.array_equal(g["kept"].cpu().numpy(), ref["kept"]) and np.array_equal(g["thr"].cpu().numpy().view(np.uint32), ref["thr"])
+    assert compare_caches(device_cache_to_host(w, g["dst"]), ref["cache"])
+    o, orf = g["out"].cpu().numpy(), ref["out"]
+    assert attn_error(o[:, 1:3], orf[:, 1:3]) <= ATTN_TOL
+    assert np.all(o[:, 0] == 7.0) and np.all(o[:, 3] == 7.0)      # layers outside the range are not written
+
+
+def test_device_side_errors():
+    w = wl(1, 1, 4, 2, 64)
+    seg_len = [300, 10, 0, 500]
+    c, now = ki.ragged_cache(w, seg_len, reserve=1, salt=14)
+    g, _ = _one_step(w, c, now, [10 ** 6], 1, hint=4, dst_cap=800)        # 814 survivors + reserve do not fit 800
+    assert g["status"] == -4
+    assert torch.all(g["out"] == 7.0)                                      # the later kernels did nothing
+    c2, now2 = ki.ragged_cache(w, seg_len, reserve=1, salt=14)
+    g, _ = _one_step(w, c2, now2, [10 ** 6], 1, hint=4, n_new=2)           # two tokens where one slot is reserved
+    assert g["status"] == -4
+    assert g["src"].seg_len.cpu().tolist() == seg_len                      # no segment took its tokens
