@@ -394,8 +394,12 @@ class Runner:
             pc = self.pc
             kv.kvtrim_paged_append(ctx, pc, inp["k_new"], inp["v_new"], inp["log_beta_new"], self.pos_news[s],
                                    log_tail_new=inp.get("log_tail_new"))
-            kv.kvtrim_paged_score(ctx, pc, self.nows[s], self.score)
-            kv.kvtrim_paged_select(ctx, pc, self.score, self.budget, self.keep, self.kept, self.thr)
+            if a.separate_score_select:
+                kv.kvtrim_paged_score(ctx, pc, self.nows[s], self.score)
+                kv.kvtrim_paged_select(ctx, pc, self.score, self.budget, self.keep, self.kept, self.thr)
+            else:
+                kv.kvtrim_paged_score_select(ctx, pc, self.nows[s], self.budget, self.score, self.keep, self.kept, self.thr,
+                                             evict_hint=self.per_seq)
             kv.kvtrim_paged_evict(ctx, pc, self.keep)
             if a.defrag_every and s % a.defrag_every == 0:
                 kv.kvtrim_paged_defrag(ctx, pc)
@@ -451,7 +455,9 @@ def moved_bytes(w, a, n_cand, n_ret, rows_written_in_place=None):
     nq = w.n_seq * w.n_layers * w.n_q_heads
     one_call = not (a.paged or a.inplace or a.unfused or a.separate_score_select or a.separate_calls)
     m = {"append": 2 * R * w.nseg}
-    if a.separate_score_select or a.paged:
+    if a.paged and not a.separate_score_select:
+        m["paged_score_select"] = (8 + tail + 4 + 4 + 4 + 1) * n_cand   # scoring pass (score out), mask pass (score and position in, mask out)
+    elif a.separate_score_select or a.paged:
         m["score"] = (8 + tail + 4) * n_cand                       # log beta, position (, tail) in; score out
         m["select"] = (3 * 4 + 4 + 1) * n_cand                     # three histogram passes and the mask pass read the score; mask out
     elif one_call:
@@ -634,7 +640,7 @@ def run_decode(args, brief=False):
         f"calls move ({100 * moved_total / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS:.1f} % of peak); stage model "
         f"{alg_total / 1e9:.3f} GB -> {alg_total / (ms_per_step * 1e-3) / 1e9:.0f} GB/s; {dom} {dom_avg_ms:.4f} ms "
         f"({achieved:.0f} GB/s on its compulsory bytes)")
-    if not (args.separate_score_select or args.paged):
+    if not args.separate_score_select:
         log(f"[bench] decode-step selections: {sel_paths[0]} from the candidate list, {sel_paths[1]} by the single-block fallback")
     second = None
     if args.unfused and args.inplace:
@@ -650,7 +656,8 @@ def run_decode(args, brief=False):
           {"fused": "", "paged": "_paged", "inplace": "_inplace", "unfused": "_unfused"}[variant]
     one_call = not (args.paged or args.inplace or args.unfused or args.separate_score_select or args.separate_calls)
     calls = ("decode_step (append, stages 1-4 in one call; three kernels per decode step)" if one_call else
-             "paged_append, paged_score, paged_select, paged_evict, paged_attn (paged layout: no K/V moved)" if args.paged else
+             ("paged_append, " + ("paged_score, paged_select" if args.separate_score_select else "paged_score_select") +
+              ", paged_evict, paged_attn (paged layout: no K/V moved)") if args.paged else
              ("append, " + ("score, select_global" if args.separate_score_select else "score_select") + ", " +
               ("compact, decode_attn" if args.unfused and not args.inplace else
                "compact_inplace, decode_attn" if args.unfused else
@@ -703,7 +710,7 @@ def run_decode(args, brief=False):
                      "stage_model_achieved": (stage_model_bytes / (dom_avg_ms * 1e-3) / 1e9) if stage_model_bytes else None,
                      "second_kernel": second},
     }
-    if not (args.separate_score_select or args.paged):
+    if not args.separate_score_select:
         result["config"]["decode_step_selection"] = {"from_candidate_list": sel_paths[0], "single_block_fallback": sel_paths[1]}
     if moved_rows is not None:
         result["config"]["in_place"] = {"room": args.inplace, "rows_written_sampled": moved_rows, "rows_retained": n_ret}
@@ -906,7 +913,7 @@ def main():
                     help="run stages 1 and 2 as two calls (kvtrim_score, kvtrim_select_global) instead of kvtrim_score_select")
     ap.add_argument("--paged", action="store_true",
                     help="steady state on the paged layout: eviction frees slots of fixed-size pages and moves no K/V "
-                         "(paged_append, paged_score, paged_select, paged_evict, paged_attn)")
+                         "(paged_append, paged_score_select, paged_evict, paged_attn)")
     ap.add_argument("--defrag-every", type=int, default=0, metavar="N",
                     help="with --paged: defragment the pages every N steps (kvtrim_paged_defrag), inside the timed region")
     ap.add_argument("--kernel-times", action="store_true",

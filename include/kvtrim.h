@@ -380,6 +380,17 @@ kvtrim_status kvtrim_paged_select(kvtrim_ctx *ctx, const kvtrim_paged_cache *c, 
                                   const int64_t *budget, uint8_t *keep_out, int32_t *kept_out,
                                   uint32_t *thr_key_out, void *hip_stream);
 
+/* Stages 1 + 2 on the paged layout in one call: leaves in score_out, keep_out, kept_out and thr_key_out exactly
+ * what kvtrim_paged_score followed by kvtrim_paged_select leave there.  evict_hint as in kvtrim_score_select:
+ * 0 runs those two calls' kernels; a small positive value - about the number of entries a sequence loses in this
+ * step - takes the decode-step form (Sec. 4.2: a decode step evicts about as many entries as it appended): two
+ * kernels that walk every segment's slots through its block table, the first scoring them and ranking the few
+ * candidates below a bound carried from the previous call, the second writing the mask.  The result does not
+ * depend on the hint; a hint that does not fit costs one slow single-block selection. */
+kvtrim_status kvtrim_paged_score_select(kvtrim_ctx *ctx, const kvtrim_paged_cache *c, const int32_t *now,
+                                        const int64_t *budget, float *score_out, uint8_t *keep_out, int32_t *kept_out,
+                                        uint32_t *thr_key_out, int64_t evict_hint, void *hip_stream);
+
 /* Stage 3 on the paged layout: live slots with keep[e] == 0 become empty; pages left without a
  * live entry return to the free list and leave their segment's block table.  No K/V moves. */
 kvtrim_status kvtrim_paged_evict(kvtrim_ctx *ctx, kvtrim_paged_cache *c, const uint8_t *keep, void *hip_stream);

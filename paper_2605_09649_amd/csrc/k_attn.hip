@@ -109,10 +109,12 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
     __shared__ float s_o[NSTREAM][G][D];
 
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    const int ch = blockIdx.x;                                    // (the grid never exceeds the tables)
     const int total = ws.att_chunk_prefix[sh.nseg];
-    const int ch = blockIdx.x;
+    const ChunkDesc cd = ws.att_desc[ch];                         // requested together with the count ...
+    int4 pgs = make_int4(0, 0, 0, 0);
+    if (PAGED) pgs = reinterpret_cast<const int4*>(ws.att_pages)[ch];   // ... and with the chunk's pages
     if (ch >= total) return;
-    const ChunkDesc cd = ws.att_desc[ch];
     const int seg = cd.seg;
     const int off = 0, row_end = cd.n;                            // rows [0, n) counted from cd.first
     const int64_t base = cd.first;
@@ -139,22 +141,25 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
     const vec* vp = reinterpret_cast<const vec*>(c.v);
     constexpr int VPR = D / E;                                    // vectors per row = 16
 
-    // PAGED: the (at most four) pages of the run, looked up once so that no load of the loop waits for them
-    int pg0 = 0, pg1 = 0, pg2 = 0, pg3 = 0;
+    // PAGED: the (at most four) pages of the run come from the plan kernel's table beside the descriptors, so no
+    // load of the loop waits for a look-up in the block table
+    int pg0 = 0, pg1 = 0, pg2 = 0, pg3 = 0, full = 0;             // full: bit i = page i of the run has no empty slot
     if (PAGED) {
-        const int32_t* bt = ws.pg_block_table + base;
         const int np = row_end >> 7, hi = (int)(c.cap >> 7) - 1;
-        pg0 = min(max(bt[0], 0), hi);
-        pg1 = np > 1 ? min(max(bt[1], 0), hi) : 0;
-        pg2 = np > 2 ? min(max(bt[2], 0), hi) : 0;
-        pg3 = np > 3 ? min(max(bt[3], 0), hi) : 0;
+        pg0 = min(max(pgs.x & ~ATT_PAGE_FULL, 0), hi);
+        pg1 = np > 1 ? min(max(pgs.y & ~ATT_PAGE_FULL, 0), hi) : 0;
+        pg2 = np > 2 ? min(max(pgs.z & ~ATT_PAGE_FULL, 0), hi) : 0;
+        pg3 = np > 3 ? min(max(pgs.w & ~ATT_PAGE_FULL, 0), hi) : 0;
+        full = (pgs.x >= ATT_PAGE_FULL) | ((pgs.y >= ATT_PAGE_FULL) << 1) | ((pgs.z >= ATT_PAGE_FULL) << 2) | ((pgs.w >= ATT_PAGE_FULL) << 3);
     }
 
     for (int r0 = off + wave * 16; r0 < row_end; r0 += 64) {
         const int last = row_end - 1;
         int64_t rbase = base;                                     // entry of row 0 in this 16-row group's numbering
+        bool holes = PAGED;                                       // the group's page may have empty slots: look at the positions
         if (PAGED) {                                              // 16 | page size: the group lies in one page
             const int pi = r0 >> 7;
+            holes = !((full >> pi) & 1);
             const int pg = pi == 0 ? pg0 : (pi == 1 ? pg1 : (pi == 2 ? pg2 : pg3));
             rbase = (int64_t)pg * KVTRIM_PAGE_SIZE - (r0 & ~(KVTRIM_PAGE_SIZE - 1));
         }
@@ -180,7 +185,7 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
             float zi = acc[i] * scale_log2;
             if (SOFT) zi = fmaf((float)(t_now - c.pos[e]) * c.log_beta[e], 1.4426950408889634f, zi);
             bool valid = row < row_end;
-            if (PAGED) {
+            if (PAGED && holes) {                                 // (uniform over the wavefront)
                 valid = valid && c.pos[e] >= 0;
                 if (!valid) vf[i] = F::zero();
             }

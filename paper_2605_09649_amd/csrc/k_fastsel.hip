@@ -45,22 +45,40 @@ __device__ __forceinline__ int seg_checked_len(const CacheView& c, int g, int ns
 // A segment as the kernels see it.  STEP: its entries [len_old, len) are this step's new tokens - up to the first
 // padding row (negative position), none if the segment has no room for them (kvtrim_append's rule) - whose
 // metadata is read from the new-token buffers by every block, never from the cache.
+// PAGED: the segment's entries are the slots of its pages in block-table order (entry j = slot j % 128 of the table's
+// page j / 128; start = the table's row); slots with a negative position are empty and `live` counts the others.
 struct SegView {
     int64_t start;
     int len_old;
     int len;
+    int live;
 };
 
-template <bool STEP>
+constexpr int SCAN_RAGGED = 0, SCAN_STEP = 1, SCAN_PAGED = 2;     // what k_fast_scan walks over
+
+template <int KIND>
 __device__ __forceinline__ SegView seg_view(const CacheView& c, int g, int nseg, const StepArgs& sa, bool* bad, bool* nocap) {
+    constexpr bool STEP = KIND == SCAN_STEP;
     SegView v;
+    if (KIND == SCAN_PAGED) {
+        const int npg = sa.pg.seg_pages[g], live = sa.pg.seg_live[g];
+        v.start = (int64_t)g * sa.pg.max_pps;
+        if (npg < 0 || npg > sa.pg.max_pps || live < 0 || (int64_t)live > (int64_t)npg * KVTRIM_PAGE_SIZE) {
+            *bad = true;
+            v.len_old = v.len = v.live = 0;
+            return v;
+        }
+        v.len_old = v.len = npg * KVTRIM_PAGE_SIZE;
+        v.live = live;
+        return v;
+    }
     const int len = c.seg_len[g];
     const int64_t st = c.seg_start[g];
     const int64_t nxt = g + 1 < nseg ? c.seg_start[g + 1] : c.cap;
     v.start = st;
     if (len < 0 || st < 0 || st + len > c.cap || st + len > nxt) {
         *bad = true;
-        v.len_old = v.len = 0;
+        v.len_old = v.len = v.live = 0;
         return v;
     }
     v.len_old = v.len = len;
@@ -73,6 +91,7 @@ __device__ __forceinline__ SegView seg_view(const CacheView& c, int g, int nseg,
         }
         v.len = len + cnt;
     }
+    v.live = v.len;
     return v;
 }
 
@@ -150,8 +169,9 @@ __device__ __forceinline__ void walk_from_top(ResolveShared* sm, int64_t rank) {
 // Where the key of an entry comes from: computed from log beta and the position (SCORE: stage 1 fused, Eq.
 // global_score in log domain - one fp32 multiply, or one fused multiply-add with the cached horizon tail) or
 // read from the caller's score array.  Both are inputs of the call, so any block may read any entry at any time.
-template <bool SCORE, bool STEP>
+template <bool SCORE, int KIND>
 struct KeySource {
+    static constexpr bool STEP = KIND == SCAN_STEP, PAGED = KIND == SCAN_PAGED;
     const float* score_in;
     const float* lb;
     const float* lt;
@@ -161,12 +181,21 @@ struct KeySource {
     const int32_t* pos_new;
     int n_new;
     int t1;
-    __device__ __forceinline__ int pos_at(int g, const SegView& v, int j) const {
-        if (STEP && j >= v.len_old) return pos_new[(int64_t)g * n_new + (j - v.len_old)];
-        return pos[v.start + j];
+    const int32_t* bt;                                            // PAGED: the block tables and the pool's page count
+    int n_pages;
+    // where entry j of the segment lies in the cache's arrays (not for a STEP's new tokens); *bad_page: the block
+    // table names a page outside the pool (the page is clamped into it)
+    __device__ __forceinline__ int64_t place(const SegView& v, int j, bool* bad_page) const {
+        if (!PAGED) return v.start + j;
+        int pg = bt[v.start + (j >> 7)];
+        if (pg < 0 || pg >= n_pages) {
+            *bad_page = true;
+            pg = pg < 0 ? 0 : n_pages - 1;
+        }
+        return (int64_t)pg * KVTRIM_PAGE_SIZE + (j & (KVTRIM_PAGE_SIZE - 1));
     }
-    __device__ __forceinline__ float score_at(int g, const SegView& v, int j) const {
-        if (!SCORE) return score_in[v.start + j];
+    // entry j of segment g: false for an empty slot (PAGED), else its position and score
+    __device__ __forceinline__ bool entry_at(int g, const SegView& v, int j, int* p_out, float* s_out) const {
         float b, t = 0.f;
         int p;
         if (STEP && j >= v.len_old) {
@@ -175,19 +204,32 @@ struct KeySource {
             b = lb_new[i];
             if (lt) t = lt_new[i];
         } else {
-            const int64_t e = v.start + j;
+            bool bp = false;
+            const int64_t e = place(v, j, &bp);
             p = pos[e];
+            if (PAGED && p < 0) return false;
+            if (!SCORE) {
+                *p_out = p;
+                *s_out = score_in[e];
+                return true;
+            }
             b = lb[e];
             if (lt) t = lt[e];
         }
+        *p_out = p;
+        if (!SCORE) {
+            *s_out = 0.f;                                         // (a STEP always computes its scores)
+            return true;
+        }
         const float dt = (float)(t1 - p);
-        return lt ? __fmaf_rn(dt, b, t) : __fmul_rn(dt, b);
+        *s_out = lt ? __fmaf_rn(dt, b, t) : __fmul_rn(dt, b);
+        return true;
     }
 };
 
 // One digit of a most-significant-digit radix select over all entries of the sequence, by this block alone.
-template <int PASS, bool SCORE, bool STEP>
-__device__ __forceinline__ void slow_pass(const KeySource<SCORE, STEP>& ks, const CacheView& c, const Shape& sh,
+template <int PASS, bool SCORE, int KIND>
+__device__ __forceinline__ void slow_pass(const KeySource<SCORE, KIND>& ks, const CacheView& c, const Shape& sh,
                                           const StepArgs& sa, int seq, uint32_t prefix, ResolveShared* sm) {
     constexpr int NB = PASS == 2 ? 1024 : 2048;
     const int tid = threadIdx.x;
@@ -196,19 +238,22 @@ __device__ __forceinline__ void slow_pass(const KeySource<SCORE, STEP>& ks, cons
     __syncthreads();
     for (int g = seq * sh.segs_per_seq; g < (seq + 1) * sh.segs_per_seq; ++g) {
         bool bad = false, nocap = false;
-        const SegView v = seg_view<STEP>(c, g, sh.nseg, sa, &bad, &nocap);
+        const SegView v = seg_view<KIND>(c, g, sh.nseg, sa, &bad, &nocap);
         const int len = v.len;
         for (int j0 = tid; j0 < len; j0 += FAST_THREADS * FAST_BATCH) {
             float sv[FAST_BATCH];
+            bool lv[FAST_BATCH];
 #pragma unroll
             for (int u = 0; u < FAST_BATCH; ++u) {
                 const int j = j0 + u * FAST_THREADS;
-                sv[u] = j < len ? ks.score_at(g, v, j) : 0.f;
+                int p;
+                sv[u] = 0.f;
+                lv[u] = j < len && ks.entry_at(g, v, j, &p, &sv[u]);
             }
 #pragma unroll
             for (int u = 0; u < FAST_BATCH; ++u) {
                 int bin;
-                if (j0 + u * FAST_THREADS < len && digit_of<PASS>(key_of_score(sv[u]), prefix, &bin)) atomicAdd(&sm->h[bin], 1u);
+                if (lv[u] && digit_of<PASS>(key_of_score(sv[u]), prefix, &bin)) atomicAdd(&sm->h[bin], 1u);
             }
         }
     }
@@ -217,8 +262,8 @@ __device__ __forceinline__ void slow_pass(const KeySource<SCORE, STEP>& ks, cons
 
 // Key of the entry of rank `rank` (1-based, descending key order) of the sequence; *rank_in = its rank among the
 // entries with that key, *ties = how many entries have that key.
-template <bool SCORE, bool STEP>
-__device__ __forceinline__ uint32_t slow_radix(const KeySource<SCORE, STEP>& ks, const CacheView& c, const Shape& sh,
+template <bool SCORE, int KIND>
+__device__ __forceinline__ uint32_t slow_radix(const KeySource<SCORE, KIND>& ks, const CacheView& c, const Shape& sh,
                                                const StepArgs& sa, int seq, int64_t rank, ResolveShared* sm,
                                                int64_t* rank_in, uint32_t* ties) {
     slow_pass<0>(ks, c, sh, sa, seq, 0, sm);
@@ -238,35 +283,79 @@ __device__ __forceinline__ uint32_t slow_radix(const KeySource<SCORE, STEP>& ks,
     return prefix;
 }
 
+// One digit of the radix select over the positions of segment g's entries with key == key_thr (taken as
+// 0x7fffffff - position, so that the smallest position is the largest): narrows *prefix and *rank.
+template <int PASS, bool SCORE, int KIND>
+__device__ __forceinline__ void tie_pos_pass(const KeySource<SCORE, KIND>& ks, int g, const SegView& v, uint32_t key_thr,
+                                             uint32_t* prefix, int64_t* rank, ResolveShared* sm) {
+    constexpr int NB = PASS == 2 ? 1024 : 2048;
+    const int tid = threadIdx.x;
+    __syncthreads();
+    for (int i = tid; i < NB; i += FAST_THREADS) sm->h[i] = 0;
+    __syncthreads();
+    for (int j = tid; j < v.len; j += FAST_THREADS) {
+        int pj, bin;
+        float sc;
+        if (ks.entry_at(g, v, j, &pj, &sc) && key_of_score(sc) == key_thr &&
+            digit_of<PASS>(0x7fffffffu - (uint32_t)pj, *prefix, &bin))
+            atomicAdd(&sm->h[bin], 1u);
+    }
+    __syncthreads();
+    walk_from_top<NB>(sm, *rank);
+    *prefix = PASS == 0 ? (uint32_t)sm->digit : (*prefix << (PASS == 1 ? RADIX_BITS1 : RADIX_BITS2)) | (uint32_t)sm->digit;
+    *rank = sm->rank_in;
+}
+
 // The `quota`-th entry (1-based) with key == key_thr in (segment ascending, position ascending) order:
 // result in sm->found_seg / sm->found_pos.  The caller guarantees that it exists.
-template <bool SCORE, bool STEP>
-__device__ __forceinline__ void slow_tie_walk(const KeySource<SCORE, STEP>& ks, const CacheView& c, const Shape& sh,
+template <bool SCORE, int KIND>
+__device__ __forceinline__ void slow_tie_walk(const KeySource<SCORE, KIND>& ks, const CacheView& c, const Shape& sh,
                                               const StepArgs& sa, int seq, uint32_t key_thr, int64_t quota,
                                               ResolveShared* sm) {
     const int tid = threadIdx.x;
     int64_t need = quota;
+    auto is_tie = [&](int g, const SegView& v, int j, int* p) {
+        float sc;
+        return j < v.len && ks.entry_at(g, v, j, p, &sc) && key_of_score(sc) == key_thr;
+    };
     for (int g = seq * sh.segs_per_seq; g < (seq + 1) * sh.segs_per_seq; ++g) {
         bool bad = false, nocap = false;
-        const SegView v = seg_view<STEP>(c, g, sh.nseg, sa, &bad, &nocap);
+        const SegView v = seg_view<KIND>(c, g, sh.nseg, sa, &bad, &nocap);
         const int len = v.len;
-        int mine = 0;
-        for (int j = tid; j < len; j += FAST_THREADS) mine += key_of_score(ks.score_at(g, v, j)) == key_thr;
+        int mine = 0, p;
+        for (int j = tid; j < len; j += FAST_THREADS) mine += is_tie(g, v, j, &p);
         const int in_seg = block_sum<int32_t>(mine, sm->lds32);
         if (need > in_seg) {
             need -= in_seg;
             continue;
         }
+        if (KIND == SCAN_PAGED) {
+            // the entry is in this segment, whose slots are in no particular order: the need-th smallest position
+            // among its ties is the need-th largest of 0x7fffffff - position - three digits, as for the keys
+            uint32_t prefix = 0;
+            int64_t rank = need;
+            tie_pos_pass<0>(ks, g, v, key_thr, &prefix, &rank, sm);
+            tie_pos_pass<1>(ks, g, v, key_thr, &prefix, &rank, sm);
+            tie_pos_pass<2>(ks, g, v, key_thr, &prefix, &rank, sm);
+            __syncthreads();
+            if (tid == 0) {
+                sm->found_seg = g;
+                sm->found_pos = (int)(0x7fffffffu - prefix);
+            }
+            __syncthreads();
+            return;
+        }
         // the entry is in this segment: entries are stored in position order
         int64_t running = 0;
         for (int base = 0; base < len; base += FAST_THREADS) {    // uniform trip count
             const int j = base + tid;
-            const int is_eq = j < len && key_of_score(ks.score_at(g, v, j)) == key_thr;
+            int pj = 0;
+            const int is_eq = is_tie(g, v, j, &pj);
             int32_t tot;
             const int32_t ex = block_excl_scan<int32_t>(is_eq, sm->lds32, &tot);
             if (is_eq && running + ex == need - 1) {
                 sm->found_seg = g;
-                sm->found_pos = ks.pos_at(g, v, j);
+                sm->found_pos = pj;
             }
             running += tot;
             if (running >= need) break;                           // uniform: tot comes from LDS
@@ -298,12 +387,13 @@ __device__ __forceinline__ void st_dev(T* p, T v) { __hip_atomic_store(p, v, __A
 // writer waits for before it arrives, and read with device-scope loads - so no block needs a fence, which on this
 // chip means a write-back of a whole L2.  The scores written here are read by the NEXT kernel only; the
 // single-block select, which has to look at every entry, recomputes them from the call's inputs.
-template <bool SCORE, bool STEP>
+template <bool SCORE, int KIND>
 __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const int32_t* __restrict__ now,
                                                             const float* score_in, float* score_out,
                                                             const int64_t* __restrict__ budget, Shape sh, Workspace ws,
                                                             int bps, int32_t* __restrict__ kept_out,
                                                             uint32_t* __restrict__ thr_out, StepArgs sa) {
+    constexpr bool STEP = KIND == SCAN_STEP, PAGED = KIND == SCAN_PAGED;
     static_assert(!STEP || SCORE, "the one-call step computes the scores itself");
     __shared__ ResolveShared sm;
     __shared__ int s_last, s_ncand;
@@ -332,7 +422,7 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
     if (tid == 0) s_ncand = 0;
     __syncthreads();
     bool bad = false, nocap = false;
-    const SegView sv0 = seg_view<STEP>(c, seg, sh.nseg, sa, &bad, &nocap);
+    const SegView sv0 = seg_view<KIND>(c, seg, sh.nseg, sa, &bad, &nocap);
     const int64_t start = sv0.start;
     const int len = sv0.len;
     if (tid == 0 && part == 0 && !tables_only && (bad || nocap)) atomicOr(ws.err, bad ? ERR_LAYOUT : ERR_CAP);
@@ -346,7 +436,9 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
     uint32_t* sub_count = ws.fl_count + (size_t)seq * FAST_SUB;
     uint32_t* grp_min = ws.fast_min + (size_t)seq * FAST_SUB;
     uint32_t* done = ws.fast_done + (size_t)seq * (FAST_SUB + 1);
-    KeySource<SCORE, STEP> ks;
+    KeySource<SCORE, KIND> ks;
+    ks.bt = sa.pg.block_table;
+    ks.n_pages = sa.pg.n_pages;
     ks.score_in = score_in;
     ks.lb = c.log_beta;
     ks.lt = c.log_tail;
@@ -382,7 +474,7 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
         int before = 0;
         for (int g = tid; g < seg; g += FAST_THREADS) {
             bool b2 = false, n2 = false;
-            const SegView v = seg_view<STEP>(c, g, sh.nseg, sa, &b2, &n2);
+            const SegView v = seg_view<KIND>(c, g, sh.nseg, sa, &b2, &n2);
             before += (v.len + CMP_CHUNK - 1) / CMP_CHUNK;
         }
         before = block_sum<int32_t>(before, sm.lds32);
@@ -409,6 +501,15 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
         for (int j0 = part * FAST_THREADS + tid; j0 < len; j0 += bps * FAST_THREADS * FAST_BATCH) {
             float sv[FAST_BATCH];
             int pv[FAST_BATCH];
+            int64_t at[FAST_BATCH];                               // where the entry lies in the arrays
+            bool bad_page = false;
+#pragma unroll
+            for (int u = 0; u < FAST_BATCH; ++u) {
+                const int j = j0 + u * bps * FAST_THREADS;
+                const bool isnew = STEP && j >= sv0.len_old;
+                at[u] = isnew ? (int64_t)seg * sa.n_new + (j - sv0.len_old) : (j < len ? ks.place(sv0, j, &bad_page) : 0);
+            }
+            if (PAGED && bad_page) atomicOr(ws.err, ERR_LAYOUT);
             if (SCORE) {
                 float lbv[FAST_BATCH], ltv[FAST_BATCH];
 #pragma unroll
@@ -416,36 +517,37 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
                     const int j = j0 + u * bps * FAST_THREADS;
                     const bool in = j < len;
                     const bool isnew = STEP && j >= sv0.len_old;
-                    const int64_t at = isnew ? (int64_t)seg * sa.n_new + (j - sv0.len_old) : start + j;
-                    pv[u] = in ? (isnew ? sa.pos_new : c.pos)[at] : 0;
-                    lbv[u] = in ? (isnew ? sa.lb_new : c.log_beta)[at] : 0.f;
-                    ltv[u] = (in && c.log_tail) ? (isnew ? sa.lt_new : c.log_tail)[at] : 0.f;
+                    pv[u] = in ? (isnew ? sa.pos_new : c.pos)[at[u]] : 0;
+                    lbv[u] = in ? (isnew ? sa.lb_new : c.log_beta)[at[u]] : 0.f;
+                    ltv[u] = (in && c.log_tail) ? (isnew ? sa.lt_new : c.log_tail)[at[u]] : 0.f;
                 }
 #pragma unroll
                 for (int u = 0; u < FAST_BATCH; ++u) {
                     const int j = j0 + u * bps * FAST_THREADS;
                     const float dt = (float)(ks.t1 - pv[u]);
                     sv[u] = c.log_tail ? __fmaf_rn(dt, lbv[u], ltv[u]) : __fmul_rn(dt, lbv[u]);
-                    if (j < len) score_out[start + j] = sv[u];
+                    if (PAGED && pv[u] < 0) sv[u] = 0.f;          // an empty slot's score reads 0
+                    if (j < len) score_out[STEP ? start + j : at[u]] = sv[u];
                 }
             } else {
 #pragma unroll
                 for (int u = 0; u < FAST_BATCH; ++u) {
                     const int j = j0 + u * bps * FAST_THREADS;
-                    sv[u] = j < len ? score_in[start + j] : 0.f;
-                    pv[u] = 0;
+                    sv[u] = j < len ? score_in[at[u]] : 0.f;
+                    pv[u] = (PAGED && j < len) ? c.pos[at[u]] : 0;
                 }
             }
 #pragma unroll
             for (int u = 0; u < FAST_BATCH; ++u) {
                 const int j = j0 + u * bps * FAST_THREADS;
                 const uint32_t key = key_of_score(sv[u]);
-                if (j < len) mn = min(mn, key);
-                if (j < len && key < hi) {                        // rare: a few hundred entries per sequence and call
+                const bool live = j < len && (!PAGED || pv[u] >= 0);
+                if (live) mn = min(mn, key);
+                if (live && key < hi) {                           // rare: a few hundred entries per sequence and call
                     const int slot = atomicAdd(&s_ncand, 1);
                     if (slot < FAST_STAGE) {
                         c_key[slot] = key;
-                        c_pos[slot] = SCORE ? pv[u] : c.pos[start + j];
+                        c_pos[slot] = (SCORE || PAGED) ? pv[u] : c.pos[at[u]];
                         if (STEP) c_idx[slot] = j;
                     }
                 }
@@ -527,7 +629,7 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
         int chunks_before = 0;
         for (int g = tid; g < sh.nseg; g += FAST_THREADS) {
             bool b2 = false, n2 = false;
-            const SegView v = seg_view<STEP>(c, g, sh.nseg, sa, &b2, &n2);
+            const SegView v = seg_view<KIND>(c, g, sh.nseg, sa, &b2, &n2);
             if (v.len) atomicAdd(&s_seqcnt[g / sh.segs_per_seq], v.len);
             if (g < g0) chunks_before += (v.len + CMP_CHUNK - 1) / CMP_CHUNK;
             if (g >= g0 && g < g0 + sh.segs_per_seq) kept_out[g] = 0;
@@ -550,9 +652,8 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
         __syncthreads();
     } else {
         for (int g = g0 + tid; g < g0 + sh.segs_per_seq; g += FAST_THREADS) {
-            int64_t st;
-            bool b2 = false;
-            cnt += seg_checked_len(c, g, sh.nseg, &st, &b2);
+            bool b2 = false, n2 = false;
+            cnt += seg_view<KIND>(c, g, sh.nseg, sa, &b2, &n2).live;
             kept_out[g] = 0;                                      // the mask kernel adds its counts
         }
     }
@@ -769,7 +870,7 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
             int64_t my_start = 0;
             if (tid < nsg) {
                 bool b2 = false, n2 = false;
-                const SegView v = seg_view<STEP>(c, g0 + tid, sh.nseg, sa, &b2, &n2);
+                const SegView v = seg_view<KIND>(c, g0 + tid, sh.nseg, sa, &b2, &n2);
                 my_len = v.len;
                 my_start = v.start;
                 my_ev = s_ev[tid];
@@ -860,15 +961,18 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
             const int lane = lane_id(), wave = tid >> 6;
             for (int g = g0; g < g0 + nsg; ++g) {
                 bool b2 = false, n2 = false;
-                const SegView v = seg_view<STEP>(c, g, sh.nseg, sa, &b2, &n2);
+                const SegView v = seg_view<KIND>(c, g, sh.nseg, sa, &b2, &n2);
                 int64_t running = 0;
                 for (int t0 = 0; t0 < v.len; t0 += FAST_THREADS) {   // tiles of 8 chunks
                     const int j = t0 + tid;
                     bool kf = false;
                     if (j < v.len) {
                         if (out.mode == FSEL_THRESHOLD) {
-                            const uint32_t kk = key_of_score(ks.score_at(g, v, j));
-                            kf = !evicted_before(kk, g, kk == out.key_thr ? ks.pos_at(g, v, j) : 0, out.key_thr, out.seg_thr, out.pos_thr);
+                            int pj;
+                            float sj;
+                            ks.entry_at(g, v, j, &pj, &sj);
+                            const uint32_t kk = key_of_score(sj);
+                            kf = !evicted_before(kk, g, pj, out.key_thr, out.seg_thr, out.pos_thr);
                         } else {
                             kf = out.mode == FSEL_ALL;
                         }
@@ -905,46 +1009,55 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
 }
 
 // keep[e] from the published triple; survivors per segment are added to kept_out (zeroed by k_fast_scan).
+// PAGED: the segment's slots through its block table; an empty slot's byte is 0.
+template <bool PAGED>
 __global__ __launch_bounds__(FAST_THREADS) void k_fast_mask(CacheView c, const float* __restrict__ score, Shape sh,
                                                             Workspace ws, int bps, uint8_t* __restrict__ keep,
-                                                            int32_t* __restrict__ kept_out) {
+                                                            int32_t* __restrict__ kept_out, PagedArgs pg) {
     __shared__ int32_t lds32[17];
     const int tid = threadIdx.x;
     const int seg = blockIdx.x / bps, part = blockIdx.x % bps;
     const int seq = seg / sh.segs_per_seq;
-    int64_t start;
-    bool bad = false;
-    const int len = seg_checked_len(c, seg, sh.nseg, &start, &bad);
+    StepArgs sa{};
+    sa.pg = pg;
+    bool bad = false, nocap = false;
+    const SegView v = seg_view<PAGED ? SCAN_PAGED : SCAN_RAGGED>(c, seg, sh.nseg, sa, &bad, &nocap);
+    const int len = v.len;
+    KeySource<false, PAGED ? SCAN_PAGED : SCAN_RAGGED> ks;
+    ks.bt = pg.block_table;
+    ks.n_pages = pg.n_pages;
     const FastSel fs = ws.fast_sel[seq];
-    const float* s = score + start;
-    const int32_t* pos = c.pos + start;
-    uint8_t* kp = keep + start;
     int n = 0;
-    if (fs.mode != FSEL_THRESHOLD) {
-        const uint8_t v = fs.mode == FSEL_ALL;
-        for (int j = part * FAST_THREADS + tid; j < len; j += bps * FAST_THREADS) {
-            kp[j] = v;
-            n += v;
+    const bool seg_before = seg < fs.seg_thr, seg_same = seg == fs.seg_thr;
+    for (int j0 = part * FAST_THREADS + tid; j0 < len; j0 += bps * FAST_THREADS * FAST_BATCH) {
+        int64_t at[FAST_BATCH];
+        bool bp = false;
+#pragma unroll
+        for (int u = 0; u < FAST_BATCH; ++u) {
+            const int j = j0 + u * bps * FAST_THREADS;
+            at[u] = j < len ? ks.place(v, j, &bp) : 0;
         }
-    } else {
-        const bool seg_before = seg < fs.seg_thr, seg_same = seg == fs.seg_thr;
-        for (int j0 = part * FAST_THREADS + tid; j0 < len; j0 += bps * FAST_THREADS * FAST_BATCH) {
-            float sv[FAST_BATCH];
+        float sv[FAST_BATCH];
+        int pv[FAST_BATCH];
 #pragma unroll
-            for (int u = 0; u < FAST_BATCH; ++u) {
-                const int j = j0 + u * bps * FAST_THREADS;
-                sv[u] = j < len ? s[j] : 0.f;
-            }
+        for (int u = 0; u < FAST_BATCH; ++u) {
+            const int j = j0 + u * bps * FAST_THREADS;
+            sv[u] = (j < len && fs.mode == FSEL_THRESHOLD) ? score[at[u]] : 0.f;
+            pv[u] = (PAGED && j < len) ? c.pos[at[u]] : 0;
+        }
 #pragma unroll
-            for (int u = 0; u < FAST_BATCH; ++u) {
-                const int j = j0 + u * bps * FAST_THREADS;
-                if (j < len) {
+        for (int u = 0; u < FAST_BATCH; ++u) {
+            const int j = j0 + u * bps * FAST_THREADS;
+            if (j < len) {
+                bool kf = fs.mode == FSEL_ALL;
+                if (fs.mode == FSEL_THRESHOLD) {
                     const uint32_t key = key_of_score(sv[u]);
-                    bool kf = key > fs.key_thr;
-                    if (key == fs.key_thr) kf = seg_before || (seg_same && pos[j] <= fs.pos_thr);
-                    kp[j] = kf;
-                    n += kf;
+                    kf = key > fs.key_thr;
+                    if (key == fs.key_thr) kf = seg_before || (seg_same && (PAGED ? pv[u] : c.pos[at[u]]) <= fs.pos_thr);
                 }
+                if (PAGED && pv[u] < 0) kf = false;
+                keep[at[u]] = kf;
+                n += kf;
             }
         }
     }
@@ -964,9 +1077,29 @@ kvtrim_status launch_score_select(kvtrim_ctx* ctx, const CacheView& c, const int
     bps = bps < 1 ? 1 : (bps > 64 ? 64 : bps);
     const dim3 grid((unsigned)(sh.nseg * bps)), block(FAST_THREADS);
     { ProfScope prof(ctx, K_FAST_SCAN, st);
-      hipLaunchKernelGGL((k_fast_scan<true, false>), grid, block, 0, st, c, now, (const float*)nullptr, score, budget, sh, ws, (int)bps, kept, thr, StepArgs()); }
+      hipLaunchKernelGGL((k_fast_scan<true, SCAN_RAGGED>), grid, block, 0, st, c, now, (const float*)nullptr, score, budget, sh, ws, (int)bps, kept, thr, StepArgs()); }
     { ProfScope prof(ctx, K_FAST_MASK, st);
-      hipLaunchKernelGGL(k_fast_mask, grid, block, 0, st, c, (const float*)score, sh, ws, (int)bps, keep, kept); }
+      hipLaunchKernelGGL(k_fast_mask<false>, grid, block, 0, st, c, (const float*)score, sh, ws, (int)bps, keep, kept, PagedArgs()); }
+    KVTRIM_HIP(ctx, hipGetLastError());
+    return KVTRIM_OK;
+}
+
+// The decode-step form over a paged cache (`pool`: the page pool's arrays, cap = its slots): the same two kernels,
+// walking every segment's slots through its block table.  The caller has checked that the hint fits the list.
+kvtrim_status launch_score_select_paged(kvtrim_ctx* ctx, const CacheView& pool, const PagedArgs& pg, const int32_t* now,
+                                        const int64_t* budget, float* score, uint8_t* keep, int32_t* kept, uint32_t* thr,
+                                        hipStream_t st) {
+    const Shape& sh = ctx->shape;
+    const Workspace& ws = ctx->ws;
+    int64_t bps = pool.cap / ((int64_t)sh.nseg * FAST_ENTRIES_PER_BLOCK);
+    bps = bps < 1 ? 1 : (bps > 64 ? 64 : bps);
+    const dim3 grid((unsigned)(sh.nseg * bps)), block(FAST_THREADS);
+    StepArgs sa{};
+    sa.pg = pg;
+    { ProfScope prof(ctx, K_FAST_SCAN, st);
+      hipLaunchKernelGGL((k_fast_scan<true, SCAN_PAGED>), grid, block, 0, st, pool, now, (const float*)nullptr, score, budget, sh, ws, (int)bps, kept, thr, sa); }
+    { ProfScope prof(ctx, K_FAST_MASK, st);
+      hipLaunchKernelGGL(k_fast_mask<true>, grid, block, 0, st, pool, (const float*)score, sh, ws, (int)bps, keep, kept, pg); }
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;
 }
@@ -978,7 +1111,7 @@ kvtrim_status launch_step_scan(kvtrim_ctx* ctx, const CacheView& c, const int32_
     int64_t bps = c.cap / ((int64_t)sh.nseg * FAST_ENTRIES_PER_BLOCK);
     bps = bps < 1 ? 1 : (bps > 64 ? 64 : bps);
     ProfScope prof(ctx, K_FAST_SCAN, st);
-    hipLaunchKernelGGL((k_fast_scan<true, true>), dim3((unsigned)(sh.nseg * bps + sh.nseg)), dim3(FAST_THREADS), 0, st, c, now,
+    hipLaunchKernelGGL((k_fast_scan<true, SCAN_STEP>), dim3((unsigned)(sh.nseg * bps + sh.nseg)), dim3(FAST_THREADS), 0, st, c, now,
                        (const float*)nullptr, score, budget, sh, ctx->ws, (int)bps, kept, thr, sa);
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;

@@ -337,8 +337,10 @@ __global__ __launch_bounds__(PG4_THREADS) void k_pg_score(PagedView pc, const in
 // GROUP pages to a chunk.  prefix[g] = first chunk of segment g, prefix[nseg] = number of chunks;
 // entry_prefix (optional) counts the live entries of the segments before g.
 //   GROUP == 1: desc = {first slot of the page, page size, segment}           (selection)
-//   GROUP  > 1: desc = {index of the group's first block-table entry, slots of the group, segment}
-//               - the reader looks the pages up itself                        (attention)
+//   GROUP  > 1: desc = {index of the group's first block-table entry, slots of the group, segment},
+//               pages_out[chunk][GROUP] = the group's pages (clamped into the pool; ATT_PAGE_FULL set when
+//               every slot of the page is live), so that the reader has them with the descriptor and
+//               not one dependent load later                                  (attention)
 // Built by `nparts` blocks: every block scans the per-segment counts (a few thousand integers),
 // block `part` fills the descriptors of the segments g = part (mod nparts), one wavefront per
 // segment, and block 0 writes the prefixes.  Returns the number of chunks.  Counts that do not
@@ -347,7 +349,7 @@ __global__ __launch_bounds__(PG4_THREADS) void k_pg_score(PagedView pc, const in
 template <int GROUP, typename InRange>
 __device__ __forceinline__ int build_page_table(const PagedView& pc, int nseg, InRange in_range, int32_t* prefix,
                                                 ChunkDesc* desc, int64_t max_chunks, int64_t* entry_prefix,
-                                                int32_t* err, int part, int nparts) {
+                                                int32_t* err, int part, int nparts, int32_t* pages_out = nullptr) {
     __shared__ uint64_t s_scan[17];
     __shared__ int s_bad;
     __shared__ int s_c0[1024], s_n[1024];
@@ -399,10 +401,16 @@ __device__ __forceinline__ int build_page_table(const PagedView& pc, int nseg, I
                         d.first = (int64_t)min(max(pg, 0), pc.n_pages - 1) * P;
                         d.n = P;
                         desc[cc + i] = d;
-                    } else if (i % GROUP == 0) {
-                        d.first = row + i;
-                        d.n = P * min(GROUP, nn - i);
-                        desc[cc + i / GROUP] = d;
+                    } else {
+                        if (pages_out) {                          // (a page without an empty slot is flagged: its reader skips the positions)
+                            const int pgc = min(max(pg, 0), pc.n_pages - 1);
+                            pages_out[(int64_t)(cc + i / GROUP) * GROUP + i % GROUP] = pgc | (pc.page_live[pgc] == P ? ATT_PAGE_FULL : 0);
+                        }
+                        if (i % GROUP == 0) {
+                            d.first = row + i;
+                            d.n = P * min(GROUP, nn - i);
+                            desc[cc + i / GROUP] = d;
+                        }
                     }
                 }
                 if (__any(bad_page) && lane == 0) atomicOr(err, ERR_LAYOUT);
@@ -508,8 +516,9 @@ __global__ __launch_bounds__(1024) void k_pg_att_plan(PagedView pc, Shape sh, Wo
         const int layer = (g / H) % L;
         return layer >= layer_begin && layer < layer_end;
     };
+    static_assert(ATT_PAGE_GROUP == 4, "ws.att_pages holds four pages per chunk");
     build_page_table<ATT_PAGE_GROUP>(pc, sh.nseg, in_range, ws.att_chunk_prefix, ws.att_desc, ws.max_att_chunks, nullptr,
-                                     ws.err, blockIdx.x, gridDim.x);
+                                     ws.err, blockIdx.x, gridDim.x, ws.att_pages);
 }
 
 // Mask of the paged selection: a block takes PG_PER_BLOCK pages, a thread four consecutive slots
@@ -1042,6 +1051,29 @@ kvtrim_status kvtrim_paged_select(kvtrim_ctx* ctx, const kvtrim_paged_cache* c, 
     }
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;
+}
+
+kvtrim_status kvtrim_paged_score_select(kvtrim_ctx* ctx, const kvtrim_paged_cache* c, const int32_t* now, const int64_t* budget,
+                                        float* score_out, uint8_t* keep_out, int32_t* kept_out, uint32_t* thr_key_out,
+                                        int64_t evict_hint, void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    if (const char* p = paged_problem(ctx, c)) return bad(ctx, p);
+    if (!now || !budget || !score_out || !keep_out || !kept_out) return bad(ctx, "now / budget / score_out / keep_out / kept_out is NULL");
+    if ((((uintptr_t)score_out) & 15) || (((uintptr_t)keep_out) & 3)) return bad(ctx, "score_out not 16-byte or keep_out not 4-byte aligned");
+    // the list has to hold about 3 (k + 1) entries for k evictions, spread unevenly over its sub-lists
+    if (evict_hint <= 0 || 8 * (evict_hint + 1) > (int64_t)ctx->ws.fl_cap) {
+        const kvtrim_status rc = kvtrim_paged_score(ctx, c, now, score_out, hip_stream);
+        if (rc != KVTRIM_OK) return rc;
+        return kvtrim_paged_select(ctx, c, score_out, budget, keep_out, kept_out, thr_key_out, hip_stream);
+    }
+    PagedArgs pg;
+    pg.block_table = c->block_table;
+    pg.seg_pages = c->seg_pages;
+    pg.seg_live = c->seg_live;
+    pg.n_pages = c->n_pages;
+    pg.max_pps = c->max_pages_per_seg;
+    return launch_score_select_paged(ctx, pool_view(c), pg, now, budget, score_out, keep_out, kept_out, thr_key_out,
+                                     (hipStream_t)hip_stream);
 }
 
 kvtrim_status kvtrim_paged_evict(kvtrim_ctx* ctx, kvtrim_paged_cache* c, const uint8_t* keep, void* hip_stream) {

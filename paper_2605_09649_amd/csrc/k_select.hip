@@ -253,7 +253,7 @@ __global__ __launch_bounds__(HIST_THREADS) void k_sel_hist(const float* __restri
             // 2 (k + 1) retained entries between it and the threshold (seed_distance).  The entry of
             // that rank is walked down the three histograms as far as it shares the threshold's digits (below that
             // the histograms count other buckets); where it leaves them, the upper edge of its bucket is taken.
-            if (!PAGED && ws.fl_cap > 0 && st.count > st.want) {
+            if (ws.fl_cap > 0 && st.count > st.want) {
                 SelState sb = ws.sel[(size_t)sh.n_seq + seq];     // state before the first digit
                 const int64_t above = seed_distance(st.count - st.want, sh.segs_per_seq, ws.fl_cap);
                 sb.rank = st.want - above >= 1 ? st.want - above : 1;

@@ -100,6 +100,7 @@ static Layout layout_of(const kvtrim_config* c, bool select_only) {
     l.off[31] = bump(cur, (size_t)c->n_seq * l.fl_cap * sizeof(int32_t));      // fl_pos
     l.off[32] = bump(cur, (size_t)c->n_seq * l.fl_cap * sizeof(int32_t));      // fl_idx
     l.off[33] = bump(cur, seg_tables * (size_t)nseg * sizeof(int32_t));        // step_len
+    l.off[34] = bump(cur, l.max_att_chunks * 4 * sizeof(int32_t));             // att_pages
     l.total = (cur + 255) & ~(size_t)255;
     return l;
 }
@@ -141,6 +142,7 @@ static void bind(const Layout& l, char* b, Workspace& w) {
     w.fl_pos = (int32_t*)(b + l.off[31]);
     w.fl_idx = (int32_t*)(b + l.off[32]);
     w.step_len = (int32_t*)(b + l.off[33]);
+    w.att_pages = (int32_t*)(b + l.off[34]);
     w.fl_cap = l.fl_cap;
     w.max_sel_chunks = l.max_sel_chunks;
     w.max_cmp_chunks = l.max_cmp_chunks;
@@ -537,7 +539,7 @@ kvtrim_status kvtrim_decode_step(kvtrim_ctx* ctx, kvtrim_cache* src, const void*
     if (layer_begin < 0 || layer_end > ctx->cfg.n_layers || layer_begin >= layer_end)
         return invalid(ctx, "empty or out-of-range layer range");
     if (!(softmax_scale == softmax_scale)) return invalid(ctx, "softmax_scale is NaN");
-    StepArgs sa;
+    StepArgs sa{};
     sa.k_new = (const uint16_t*)k_new;
     sa.v_new = (const uint16_t*)v_new;
     sa.lb_new = log_beta_new;

@@ -83,8 +83,19 @@ struct FastSel {
     int32_t pos_thr;
 };
 
+// A paged cache as the decode-step selection walks it: the block tables ([nseg][max_pps] pages of the pool), pages and
+// live entries per segment.
+struct PagedArgs {
+    const int32_t* block_table;
+    const int32_t* seg_pages;
+    const int32_t* seg_live;
+    int32_t n_pages;
+    int32_t max_pps;
+};
+
 // The decode step in one call (kvtrim_decode_step): the tokens that enter the cache in this step (laid out as kvtrim_append takes them;
-// their rows also go into the source cache) and where the compaction goes.
+// their rows also go into the source cache) and where the compaction goes.  (pg: the paged form of the decode-step
+// selection, which takes neither new tokens nor a destination, hands its tables to the same kernel here.)
 struct StepArgs {
     const uint16_t* k_new;
     const uint16_t* v_new;
@@ -96,8 +107,10 @@ struct StepArgs {
     CacheViewMut dst;
     int reserve;
     uint8_t* keep_out;
+    PagedArgs pg;
 };
 
+constexpr int ATT_PAGE_FULL = 0x40000000;   // in ws.att_pages: the page has no empty slot
 constexpr int STEP_MAX_SEGS = 1024;  // segments per sequence the one-call decode step handles
 constexpr int STEP_MAX_EVICT = 1024; // evictions per sequence it lists (more: the keep mask and per-chunk offsets are written by one block)
 constexpr int STEP_MAX_SEQS = 1024;  // sequences it handles
@@ -141,6 +154,7 @@ struct Workspace {
     int32_t* cmp_chunk_prefix;   // [nseg+1]
     ChunkDesc* cmp_desc;         // [max_cmp_chunks]
     int64_t* cmp_chunk_dst;      // [max_cmp_chunks] first dst entry of the chunk's survivors (| CMP_DST_FULL)
+    int32_t* att_pages;          // [max_att_chunks][4] paged attention: the pages of a chunk, beside its descriptor (| ATT_PAGE_FULL)
     int64_t* run_dst;            // [max_att_chunks] the same per run of the loop-shaped fused kernel (flag: every chunk of the run is full)
     // attention
     int32_t* att_chunk_prefix;   // [nseg+1]
@@ -205,6 +219,9 @@ kvtrim_status launch_select(kvtrim_ctx*, const CacheView&, const float* score, c
 // Stages 1 + 2 in one call.  General form: the radix passes, the first of which computes the score on the fly and
 // writes it out.  Decode-step form (evict_hint small): one pass that scores and lists the candidates below the
 // carried bound, resolved by the last block of every sequence, and the mask pass.
+kvtrim_status launch_score_select_paged(kvtrim_ctx*, const CacheView& pool, const PagedArgs&, const int32_t* now,
+                                        const int64_t* budget, float* score, uint8_t* keep, int32_t* kept, uint32_t* thr,
+                                        hipStream_t);
 kvtrim_status launch_score_select(kvtrim_ctx*, const CacheView&, const int32_t* now, const int64_t* budget, float* score,
                                   uint8_t* keep, int32_t* kept, uint32_t* thr, int64_t evict_hint, hipStream_t);
 kvtrim_status launch_step_scan(kvtrim_ctx*, const CacheView&, const int32_t* now, const int64_t* budget, float* score,

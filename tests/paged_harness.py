@@ -137,11 +137,12 @@ def ties_overflow(w, hc, score_ref, live, thr_ref, budget_np):
 
 
 def run_paged_both(w, budgets, device="cuda:0", cache_dict=None, now0=None, n_pages=None, max_pps=None, horizon=1,
-                   tweak_new=None, defrag_at=()):
+                   tweak_new=None, defrag_at=(), hint=None):
     """budgets: one per-sequence budget list per step; step 0 selects on the ragged prefill cache
     and builds the pages, the later steps run on the pages.  tweak_new(step, inputs) may edit the
     generated inputs of a step (used to plant ties).  In the steps listed in defrag_at the pages are
-    defragmented between eviction and attention.  Returns one dict of findings per step."""
+    defragmented between eviction and attention.  hint: None runs stages 1 and 2 on the pages as two calls,
+    a number runs kvtrim_paged_score_select with that evict_hint.  Returns one dict of findings per step."""
     reserve = 1
     if cache_dict is None:
         cache_dict = ki.prefill_cache(w, reserve=reserve)
@@ -203,8 +204,11 @@ def run_paged_both(w, budgets, device="cuda:0", cache_dict=None, now0=None, n_pa
         else:
             kv.kvtrim_paged_append(ctx, pc, d["k_new"], d["v_new"], d["log_beta_new"], pos_dev,
                                    log_tail_new=d.get("log_tail_new"))
-            kv.kvtrim_paged_score(ctx, pc, now_dev, score)
-            kv.kvtrim_paged_select(ctx, pc, score, budget_dev, keep, kept, thr)
+            if hint is None:
+                kv.kvtrim_paged_score(ctx, pc, now_dev, score)
+                kv.kvtrim_paged_select(ctx, pc, score, budget_dev, keep, kept, thr)
+            else:
+                kv.kvtrim_paged_score_select(ctx, pc, now_dev, budget_dev, score, keep, kept, thr, evict_hint=hint)
             res["status_select"] = kv.kvtrim_poll_error(ctx)
             pre = PagedHost(pc, rows=False)
             res["structure_pre"] = pre.structure_problems()
@@ -233,6 +237,7 @@ def run_paged_both(w, budgets, device="cuda:0", cache_dict=None, now0=None, n_pa
         res["kept_total"] = int(kept_ref.sum())
         res["pages_in_use"] = int(ph.seg_pages.sum())
         res["ties_overflow"] = ties_overflow(w, hc, score_ref, live, thr_ref, budget_np)
+        res["path_counts"] = kv.kvtrim_select_path_counts(ctx)
         results.append(res)
         hc = hc_next
     return results

@@ -20,8 +20,8 @@ class Loop:
     """Device state of one decode loop with static input buffers (so that a captured step finds its inputs at
     fixed addresses)."""
 
-    def __init__(self, w, paged, inplace=False):
-        self.w, self.paged, self.inplace = w, paged, inplace
+    def __init__(self, w, paged, inplace=False, calls="four"):
+        self.w, self.paged, self.inplace, self.calls = w, paged, inplace, calls
         self.room = 8 if inplace else 1                           # free slots behind every segment after the first step
         pre = ki.prefill_cache(w, reserve=1)
         self.src = kv.Cache.from_dict(pre, DEV)
@@ -80,9 +80,20 @@ class Loop:
             kv.kvtrim_paged_attn(ctx, self.pc, i["q"], 0, w.n_layers, self.scale, self.out[slot])
         else:
             dst = self.spare[self.flip]
+            hint = w.n_layers * w.n_kv_heads                      # evictions per sequence and step once at the budget
+            if self.calls == "decode_step":                       # the whole step in one call
+                kv.kvtrim_decode_step(ctx, self.cur, i["k_new"], i["v_new"], i["log_beta_new"], self.pos[slot], 1, self.now[slot],
+                                      self.budget, self.score, self.keep, self.kept, dst, 1, i["q"], 0, w.n_layers, self.scale,
+                                      self.out[slot], thr_key_out=self.thr, evict_hint=hint)
+                self.cur, self.flip = dst, self.flip ^ 1
+                return
             kv.kvtrim_append(ctx, self.cur, i["k_new"], i["v_new"], i["log_beta_new"], self.pos[slot], 1)
-            kv.kvtrim_score(ctx, self.cur, self.now[slot], self.score)
-            kv.kvtrim_select_global(ctx, self.cur, self.score, self.budget, self.keep, self.kept, self.thr)
+            if self.calls == "score_select":                      # stages 1 + 2 in one call, decode-step form
+                kv.kvtrim_score_select(ctx, self.cur, self.now[slot], self.budget, self.score, self.keep, self.kept, self.thr,
+                                       evict_hint=hint)
+            else:
+                kv.kvtrim_score(ctx, self.cur, self.now[slot], self.score)
+                kv.kvtrim_select_global(ctx, self.cur, self.score, self.budget, self.keep, self.kept, self.thr)
             if self.inplace:                                      # the other cache only lends its arrays
                 kv.kvtrim_compact_attn_inplace(ctx, self.cur, self.keep, self.kept, dst, i["q"], 0, w.n_layers, self.scale,
                                                self.out[slot])
@@ -118,11 +129,12 @@ def same(a, b):
                               b[k].view(np.uint8) if b[k].dtype.kind == "f" else b[k]) for k in a) and a.keys() == b.keys()
 
 
-@pytest.mark.parametrize("paged", [False, True, "inplace"])
+@pytest.mark.parametrize("paged", [False, True, "inplace", "score_select", "decode_step"])
 def test_two_captured_steps_replayed_three_times_match_the_eager_loop(paged):
     w = ki.workload("tiny", prefill=900)
+    calls = paged if paged in ("score_select", "decode_step") else "four"
     inplace, paged = paged == "inplace", paged is True
-    eager, graphed = Loop(w, paged, inplace), Loop(w, paged, inplace)
+    eager, graphed = Loop(w, paged, inplace, calls), Loop(w, paged, inplace, calls)
     for loop in (eager, graphed):
         loop.first_step()
         assert kv.kvtrim_poll_error(loop.ctx) == 0
