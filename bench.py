@@ -552,6 +552,9 @@ def run_decode(args, brief=False):
     n_cand = n_ret + w.nseg
     log(f"[bench] first step (prefill -> budget): {first_ms:.3f} ms ({first_kernels_ms:.3f} ms in its "
         f"{sum(n for _, n in prof0.values())} kernels); steady state: {n_cand} candidates, {n_ret} retained")
+    if args.kernel_times:
+        for name, (kms, n) in sorted(prof0.items(), key=lambda kvp: -kvp[1][0]):
+            log(f"[bench]   first step: {name:<18s} {1e3 * kms / n:7.1f} us x {n}")
 
     # ---- timed region: exactly K steps; the dominant kernels are bracketed by HIP events on the launch stream
     mask = (1 << 8) | (1 << 10) | (1 << 13) | (1 << 30)   # k_cmp_copy, k_att_partial, k_cmp_attn, k_att_fused

@@ -251,6 +251,36 @@ def test_fused_call_with_a_layer_range_and_sparse_mask(roomy, G, D):
     assert np.abs(lse.cpu().numpy()[:, 1:3][fin] - ref_lse[:, 1:3][fin]).max() <= 2e-3
 
 
+@pytest.mark.parametrize("D,horizon", [(128, 1), (64, 1), (128, 2)])
+def test_sparse_selection_takes_the_wavefront_per_chunk_mover(D, horizon):
+    # a destination under a quarter of the source: the row mover works a wavefront per 128-entry chunk.  One entry in
+    # sixteen survives on average; some chunks keep nothing, some keep every entry (more than one batch of 16 rows per
+    # wavefront), segments end in ragged chunks, one segment is empty.
+    w = wl(2, 2, 3, 2, D)
+    rng = np.random.default_rng(77 + D + horizon)
+    seg_len = rng.integers(1, 6000, w.nseg)
+    seg_len[3] = 0
+    seg_len[5] = 128 * 9 + 1
+    c, _ = ki.ragged_cache(w, seg_len, salt=33)
+    c = ki.with_horizon(c, horizon)
+    hc = host_cache(w, c)
+    keep_np = (rng.random(hc.cap) < 1.0 / 16).astype(np.uint8)
+    s5 = int(hc.seg_start[5])
+    keep_np[s5 + 128:s5 + 3 * 128] = 1                            # two chunks that keep everything
+    keep_np[s5 + 4 * 128:s5 + 6 * 128] = 0                        # two that keep nothing
+    keep_np[s5 + 9 * 128] = 1                                     # the one-entry tail chunk
+    kept_np = np.array([keep_np[s:s + n].sum() for s, n in zip(hc.seg_start, hc.seg_len)], np.int32)
+    dst_cap = int(kept_np.sum()) + 3 * w.nseg
+    assert dst_cap < hc.cap // 4
+    dst_ref = oracle.compact(hc, keep_np, dst_cap, 3)
+    ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, D, hc.cap)
+    dst = kv.Cache.empty(w.nseg, D, dst_cap, DEV, with_tail=horizon != 1)
+    kv.kvtrim_compact(ctx, kv.Cache.from_dict(c, DEV), torch.from_numpy(keep_np).to(DEV), torch.from_numpy(kept_np).to(DEV),
+                      dst, 3)
+    assert kv.kvtrim_poll_error(ctx) == 0
+    assert compare_caches(device_cache_to_host(w, dst), dst_ref)
+
+
 # ---------------------------------------------------------------------------------- degenerate budgets, ties
 
 def run_select_compact(w, c, now, budget, score_override=None, reserve=1):
