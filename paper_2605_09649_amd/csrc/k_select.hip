@@ -122,12 +122,45 @@ __device__ __forceinline__ SelState next_digit(const uint32_t* __restrict__ hist
 // paged one); PAGED: a slot counts only if its position is not negative.
 // SCORE (first pass of a ragged cache only): the score is computed here from log beta and the position (Eq.
 // global_score in log domain, exactly as k_score does) and written to score_w; `score` is not read.
+// VEC (ragged caches whose arrays are all 16-byte aligned): a chunk is walked in ALIGNED groups of four entries -
+// 16-byte loads, four times the bytes in flight of the entry-by-entry walk.  A group may begin before the chunk or
+// end behind it (segments start anywhere): what lies outside [first, first + n) is loaded and ignored; the one group
+// that would reach past the end of the arrays is read entry by entry.
+struct Quad {
+    int64_t a;        // first entry of the aligned group
+    int lo, hi;       // its entries a + lo .. a + hi - 1 belong to the chunk (lo == hi: none)
+    bool whole;       // all four can be loaded (the group ends inside the arrays)
+};
+__device__ __forceinline__ Quad quad_of(const ChunkDesc& d, int q, int64_t cap) {
+    Quad r;
+    r.a = (d.first & ~(int64_t)3) + 4 * (int64_t)q;
+    const int64_t end = d.first + d.n;
+    r.lo = (int)(d.first > r.a ? d.first - r.a : 0);
+    const int64_t h = end - r.a;
+    r.hi = h < r.lo ? r.lo : (h < 4 ? (int)h : 4);
+    r.whole = r.a + 4 <= cap;
+    return r;
+}
+template <typename T>
+__device__ __forceinline__ void load_quad(const T* __restrict__ base, const Quad& q, T (&v)[4]) {
+    struct alignas(16) T4 { T x, y, z, w; };
+    // (a group with nothing of the chunk, or reaching past the arrays, loads the arrays' first four entries instead)
+    const T4 x = *reinterpret_cast<const T4*>(base + ((q.whole && q.lo < q.hi) ? q.a : 0));
+    v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+}
+template <typename T>
+__device__ __forceinline__ void reload_quad_tail(const T* __restrict__ base, const Quad& q, T (&v)[4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        if (i >= q.lo && i < q.hi) v[i] = base[q.a + i];
+}
+
 template <int PASS, int SHIFT, bool PAGED, bool SCORE = false>
-__global__ __launch_bounds__(HIST_THREADS) void k_sel_hist(const float* __restrict__ score, Shape sh,
+__global__ __launch_bounds__(HIST_THREADS, 8) void k_sel_hist(const float* __restrict__ score, Shape sh,
                                                            Workspace ws, SelTables tb,
                                                            uint32_t* __restrict__ thr_out, CacheView c,
                                                            const int32_t* __restrict__ now,
-                                                           float* __restrict__ score_w) {
+                                                           float* __restrict__ score_w, bool vec) {
     static_assert(!SCORE || (PASS == 0 && !PAGED), "the score is fused into the first pass over a ragged cache only");
     constexpr int NB = PASS == 2 ? 1024 : 2048;
     constexpr int HIST_TILE = 64;
@@ -193,6 +226,63 @@ __global__ __launch_bounds__(HIST_THREADS) void k_sel_hist(const float* __restri
 #pragma unroll
                             for (int i = 0; i < 4; ++i)
                                 if (hit[i] && p[i] >= 0) atomicAdd(&h[bin[i]], 1u);
+                        }
+                    }
+                } else if (vec) {
+                    constexpr int QPC = (1 << (SHIFT - 2)) + 1;   // aligned groups of four that can overlap a chunk
+                    constexpr int U = SCORE ? 2 : 4;              // groups a thread has in flight
+                    for (int q0 = tid; q0 < nt * QPC; q0 += HIST_THREADS * U) {
+                        Quad qd[U];
+                        float sv[U][4];
+                        int pv[U][4];
+                        float lbv[U][4], ltv[U][4];
+#pragma unroll
+                        for (int u = 0; u < U; ++u) {
+                            const int qi = q0 + u * HIST_THREADS;
+                            const int cidx = qi < nt * QPC ? qi / QPC : 0;
+                            ChunkDesc d = s_desc[cidx];
+                            if (qi >= nt * QPC) d.n = 0;
+                            qd[u] = quad_of(d, qi - cidx * QPC, c.cap);
+                            if (SCORE) {
+                                load_quad(c.pos, qd[u], pv[u]);
+                                load_quad(c.log_beta, qd[u], lbv[u]);
+                                if (c.log_tail) load_quad(c.log_tail, qd[u], ltv[u]);
+                            } else {
+                                load_quad(score, qd[u], sv[u]);
+                            }
+                        }
+#pragma unroll
+                        for (int u = 0; u < U; ++u) {
+                            const Quad& q = qd[u];
+                            if (q.lo >= q.hi) continue;
+                            if (!q.whole) {                       // (once per array at most)
+                                if (SCORE) {
+                                    reload_quad_tail(c.pos, q, pv[u]);
+                                    reload_quad_tail(c.log_beta, q, lbv[u]);
+                                    if (c.log_tail) reload_quad_tail(c.log_tail, q, ltv[u]);
+                                } else {
+                                    reload_quad_tail(score, q, sv[u]);
+                                }
+                            }
+                            if (SCORE) {
+#pragma unroll
+                                for (int i = 0; i < 4; ++i) {
+                                    const float dt = (float)(t1 - pv[u][i]);
+                                    sv[u][i] = c.log_tail ? __fmaf_rn(dt, lbv[u][i], ltv[u][i]) : __fmul_rn(dt, lbv[u][i]);
+                                }
+                                if (q.whole && q.lo == 0 && q.hi == 4) {
+                                    *reinterpret_cast<float4*>(score_w + q.a) = make_float4(sv[u][0], sv[u][1], sv[u][2], sv[u][3]);
+                                } else {
+#pragma unroll
+                                    for (int i = 0; i < 4; ++i)
+                                        if (i >= q.lo && i < q.hi) score_w[q.a + i] = sv[u][i];
+                                }
+                            }
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                int bin;
+                                if (i >= q.lo && i < q.hi && digit_of<PASS>(key_of_score(sv[u][i]), prefix, &bin)) atomicAdd(&h[bin], 1u);
+                            }
                         }
                     }
                 } else {
@@ -406,13 +496,13 @@ void launch_select_passes_paged(kvtrim_ctx* ctx, const float* score, const SelTa
     const Workspace& ws = ctx->ws;
     if (pass == 0) {
         ProfScope prof(ctx, K_SEL_HIST0, st);
-        hipLaunchKernelGGL((k_sel_hist<0, 7, true>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr, CacheView(), nullptr, nullptr);
+        hipLaunchKernelGGL((k_sel_hist<0, 7, true>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr, CacheView(), nullptr, nullptr, false);
     } else if (pass == 1) {
         ProfScope prof(ctx, K_SEL_HIST1, st);
-        hipLaunchKernelGGL((k_sel_hist<1, 7, true>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr, CacheView(), nullptr, nullptr);
+        hipLaunchKernelGGL((k_sel_hist<1, 7, true>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr, CacheView(), nullptr, nullptr, false);
     } else {
         ProfScope prof(ctx, K_SEL_HIST2, st);
-        hipLaunchKernelGGL((k_sel_hist<2, 7, true>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr, CacheView(), nullptr, nullptr);
+        hipLaunchKernelGGL((k_sel_hist<2, 7, true>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr, CacheView(), nullptr, nullptr, false);
     }
 }
 
@@ -429,17 +519,20 @@ static kvtrim_status launch_select_impl(kvtrim_ctx* ctx, const CacheView& c, con
     tb.desc = ws.sel_desc;
     tb.prefix = ws.sel_chunk_prefix;
     tb.pos = nullptr;
+    // 16-byte loads need every array they touch aligned (and at least one group of four entries)
+    const bool vec = c.cap >= 4 && ((((uintptr_t)score) | ((uintptr_t)score_w) | ((uintptr_t)c.pos) | ((uintptr_t)c.log_beta) |
+                                     ((uintptr_t)c.log_tail)) & 15) == 0;
     { ProfScope prof(ctx, K_SEL_PLAN, st);
       hipLaunchKernelGGL(k_sel_plan, dim3(1 + PLAN_ZERO_BLOCKS), dim3(1024), 0, st, c, sh, budget, ws, kept, thr, hist_blocks); }
     { ProfScope prof(ctx, K_SEL_HIST0, st);
       if (now)
-          hipLaunchKernelGGL((k_sel_hist<0, SEL_SHIFT, false, true>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, (const float*)nullptr, sh, ws, tb, thr, c, now, score_w);
+          hipLaunchKernelGGL((k_sel_hist<0, SEL_SHIFT, false, true>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, (const float*)nullptr, sh, ws, tb, thr, c, now, score_w, vec);
       else
-          hipLaunchKernelGGL((k_sel_hist<0, SEL_SHIFT, false>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr, c, nullptr, nullptr); }
+          hipLaunchKernelGGL((k_sel_hist<0, SEL_SHIFT, false>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr, c, nullptr, nullptr, vec); }
     { ProfScope prof(ctx, K_SEL_HIST1, st);
-      hipLaunchKernelGGL((k_sel_hist<1, SEL_SHIFT, false>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr, c, nullptr, nullptr); }
+      hipLaunchKernelGGL((k_sel_hist<1, SEL_SHIFT, false>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr, c, nullptr, nullptr, vec); }
     { ProfScope prof(ctx, K_SEL_HIST2, st);
-      hipLaunchKernelGGL((k_sel_hist<2, SEL_SHIFT, false>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr, c, nullptr, nullptr); }
+      hipLaunchKernelGGL((k_sel_hist<2, SEL_SHIFT, false>), dim3(hist_blocks), dim3(HIST_THREADS), 0, st, score, sh, ws, tb, thr, c, nullptr, nullptr, vec); }
     { ProfScope prof(ctx, K_SEL_COUNT, st);
       hipLaunchKernelGGL(k_sel_count, dim3(n_chunk_blocks < 256 ? n_chunk_blocks : 256), dim3(CNT_THREADS), 0, st, score, sh, ws, tb, kept); }
     { ProfScope prof(ctx, K_SEL_MASK, st);

@@ -19,7 +19,7 @@ constexpr int CMP_WAVE_ROWS = 16;    // rows a wavefront moves (one batch of loa
 constexpr int CMP_THREADS = CMP_CHUNK / CMP_WAVE_ROWS * 64;   // 512: one wavefront per 16 survivors
 constexpr int RADIX_BITS0 = 11, RADIX_BITS1 = 11, RADIX_BITS2 = 10;
 constexpr int RADIX_BINS = 2048;     // bins of the widest pass
-constexpr int HIST_BLOCKS_MAX = 256; // blocks of a histogram pass (few and fat: see k_select.hip)
+constexpr int HIST_BLOCKS_MAX = 512; // blocks of a histogram pass (few and fat: see k_select.hip)
 constexpr int DONE_WORDS = 128;      // 4 sets of 32 counters (three histogram passes, the tie count)
 constexpr int HIST_REPLICAS = 8;     // copies of the merged histogram (spreads the device-scope atomics)
 
