@@ -539,7 +539,8 @@ constexpr int FUSE_RUN_ENTRIES = 2 * CMP_CHUNK;                   // source entr
 
 kvtrim_status launch_compact_attn(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const int32_t* kept,
                                   const CacheViewMut& dst, int32_t reserve, const uint16_t* q, int32_t layer_begin,
-                                  int32_t layer_end, float scale, float* out, float* lse, hipStream_t st) {
+                                  int32_t layer_end, float scale, float* out, float* lse, hipStream_t st,
+                                  int64_t evict_hint) {
     const Shape& sh = ctx->shape;
     const Workspace& ws = ctx->ws;
     const int64_t max_chunks = src.cap / CMP_CHUNK + sh.nseg;
@@ -549,7 +550,11 @@ kvtrim_status launch_compact_attn(kvtrim_ctx* ctx, const CacheView& src, const u
     // G = 1..4, 255 us at G = 5).  The loop-shaped fused kernel (k_att_fused) takes 421-423 us at head_dim 128 and
     // 242-247 us at head_dim 64 whatever the group, the two calls 553-578 us and 276-285 us.
     const bool alu_fits = sh.head_dim == 128 ? sh.group <= FUSED_ONE_SHOT_MAX_G_128 : sh.group <= FUSED_ONE_SHOT_MAX_G_64;
-    const bool sparse = dst.cap < src.cap / 4;
+    // Few survivors per source chunk?  A caller that names the evictions of the step (kvtrim_decode_step's evict_hint)
+    // has said so itself: a positive hint means a decode step, every chunk nearly whole.  Without a hint the
+    // capacities decide, in the one direction in which they can: a destination under a quarter of the source cannot
+    // take more than one source entry in four.
+    const bool sparse = evict_hint > 0 ? false : dst.cap < src.cap / 4;
     if (!sparse && !alu_fits && sh.group >= 5 && src.cap / FUSE_RUN_ENTRIES + sh.nseg <= ws.max_att_chunks &&
         max_chunks <= ws.max_cmp_chunks) {
         // Large groups of query heads: the loop-shaped fused kernel (the split-K attention kernel reading the source
@@ -641,7 +646,8 @@ kvtrim_status launch_decode_step(kvtrim_ctx* ctx, const CacheViewMut& srcm, cons
         if (rc != KVTRIM_OK) return rc;
         rc = launch_score_select(ctx, src, now, budget, score, sa.keep_out, kept, thr, evict_hint, st);
         if (rc != KVTRIM_OK) return rc;
-        return launch_compact_attn(ctx, src, sa.keep_out, kept, sa.dst, sa.reserve, q, layer_begin, layer_end, scale, out, lse, st);
+        return launch_compact_attn(ctx, src, sa.keep_out, kept, sa.dst, sa.reserve, q, layer_begin, layer_end, scale, out, lse, st,
+                                   evict_hint);
     }
     kvtrim_status rc = launch_step_scan(ctx, src, now, budget, score, kept, thr, sa, st);
     if (rc != KVTRIM_OK) return rc;

@@ -269,7 +269,7 @@ kvtrim_status launch_compact_attn_inplace(kvtrim_ctx*, const CacheViewMut& c, co
 kvtrim_status launch_compact_attn(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const int32_t* kept,
                                   const CacheViewMut& dst, int32_t reserve, const uint16_t* q,
                                   int32_t layer_begin, int32_t layer_end, float scale, float* out, float* lse,
-                                  hipStream_t);
+                                  hipStream_t, int64_t evict_hint = 0);
 // copy_rows = false: only the metadata of the new tokens enters the cache (their K/V rows stay with the caller);
 // old_len_out (or NULL) gets every segment's length before the call.
 kvtrim_status launch_append(kvtrim_ctx*, const CacheViewMut&, const uint16_t* k_new, const uint16_t* v_new,
