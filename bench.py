@@ -658,7 +658,7 @@ def run_decode(args, brief=False):
     tag = {"long": "long_128k", "llama": "llama_32k", "vlm": "vlm", "tiny": "tiny", "multiturn": "multiturn"}[w.name] + \
           {"fused": "", "paged": "_paged", "inplace": "_inplace", "unfused": "_unfused"}[variant]
     one_call = not (args.paged or args.inplace or args.unfused or args.separate_score_select or args.separate_calls)
-    calls = ("decode_step (append, stages 1-4 in one call; three kernels per decode step)" if one_call else
+    calls = ("decode_step (append, stages 1-4 in one call; three kernels per decode step where the shape allows)" if one_call else
              ("paged_append, " + ("paged_score, paged_select" if args.separate_score_select else "paged_score_select") +
               ", paged_evict, paged_attn (paged layout: no K/V moved)") if args.paged else
              ("append, " + ("score, select_global" if args.separate_score_select else "score_select") + ", " +
