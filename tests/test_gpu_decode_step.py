@@ -191,3 +191,63 @@ def test_device_side_errors():
     g, _ = _one_step(w, c2, now2, [10 ** 6], 1, hint=4, n_new=2)           # two tokens where one slot is reserved
     assert g["status"] == -4
     assert g["src"].seg_len.cpu().tolist() == seg_len                      # no segment took its tokens
+
+
+def test_more_evictions_than_the_listed_form_holds_with_the_candidates_still_listed():
+    # twelve tokens per segment and step, 64 segments: 768 evictions per step in the steady state, so the carried bound
+    # keeps about 2300 candidates listed.  Then one step whose budget drops by 400 more: its 1168 evictions are still
+    # on the list (no single-block select), but they are more than the per-segment eviction lists hold, so the last
+    # block writes the whole mask and the per-chunk offsets - then steady steps again.
+    w = wl(1, 8, 8, 2, 64)
+    n_new, reserve, steps = 12, 12, 7
+    rng = np.random.default_rng(31)
+    seg_len = rng.integers(900, 1300, w.nseg)
+    c, now = ki.ragged_cache(w, seg_len, reserve=reserve, salt=31)
+    hc = host_cache(w, c)
+    total = int(seg_len.sum())
+    cap2 = total + w.nseg * (n_new + reserve) + 8
+    caches = [kv.Cache.from_dict(c, DEV), kv.Cache.empty(w.nseg, w.head_dim, cap2, DEV), kv.Cache.empty(w.nseg, w.head_dim, cap2, DEV)]
+    n = max(caches[0].cap, cap2)
+    ctx = kv.Context(1, w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, n)
+    score = torch.zeros(n, dtype=torch.float32, device=DEV)
+    keep = torch.zeros(n, dtype=torch.uint8, device=DEV)
+    kept = torch.zeros(w.nseg, dtype=torch.int32, device=DEV)
+    thr = torch.zeros(1, dtype=torch.int32, device=DEV)
+    out = torch.zeros(1, w.n_layers, w.n_q_heads, w.head_dim, dtype=torch.float32, device=DEV)
+    lse = torch.zeros(1, w.n_layers, w.n_q_heads, dtype=torch.float32, device=DEV)
+    scale = 1.0 / math.sqrt(w.head_dim)
+    budgets = [total - 100, total - 100, total - 100, total - 100, total - 500, total - 500, total - 500]
+    hints = [0, 511, 511, 511, 511, 511, 511]
+    t = int(now.numpy()[0])
+    src = caches[0]
+    paths = []
+    for s in range(steps):
+        inp = ki.chunk_inputs(w, n_new, "cpu", 100 + s)
+        qg = torch.Generator().manual_seed(s)
+        q = torch.randn(1, w.n_layers, w.n_q_heads, w.head_dim, generator=qg).to(torch.bfloat16)
+        pos_new = np.tile(t + 1 + np.arange(n_new, dtype=np.int32), (w.nseg, 1))
+        t += n_new
+        now_np = np.array([t], np.int32)
+        bud = np.array([budgets[s]], np.int64)
+        dst = caches[1 + s % 2]
+        kv.kvtrim_decode_step(ctx, src, inp["k_new"].to(DEV), inp["v_new"].to(DEV), inp["log_beta_new"].to(DEV),
+                              torch.from_numpy(pos_new).to(DEV), n_new, torch.from_numpy(now_np).to(DEV), torch.from_numpy(bud).to(DEV),
+                              score, keep, kept, dst, reserve, q.to(DEV), 0, w.n_layers, scale, out, lse, thr_key_out=thr,
+                              evict_hint=hints[s])
+        assert kv.kvtrim_poll_error(ctx) == 0, s
+        oracle.append(hc, bf16_bits(inp["k_new"]), bf16_bits(inp["v_new"]), inp["log_beta_new"].numpy(), pos_new)
+        s_ref = oracle.score(hc, now_np)
+        keep_ref, kept_ref, thr_ref = oracle.select(hc, s_ref, bud)
+        hc = oracle.compact(hc, keep_ref, cap2, reserve)
+        out_ref, lse_ref = oracle.attend(hc, bf16_bits(q), scale)
+        assert np.array_equal(kept.cpu().numpy(), kept_ref), s
+        assert np.array_equal(thr.cpu().numpy().view(np.uint32), thr_ref), s
+        assert compare_caches(device_cache_to_host(w, dst), hc), s
+        assert attn_error(out.cpu().numpy(), out_ref) <= ATTN_TOL, s
+        src = dst
+        paths.append(kv.kvtrim_select_path_counts(ctx))
+    # the step with the budget drop found its candidates listed; so did the steady steps, but for at most one early
+    # one (768 evictions per step are more than the hint of 511 promised, and the bound seeded by the first call is
+    # placed for the hint)
+    assert paths[4][0] == paths[3][0] + 1 and paths[4][1] == paths[3][1], paths
+    assert paths[-1][1] <= 1 and paths[-1][0] >= steps - 2, paths
