@@ -251,3 +251,50 @@ def test_more_evictions_than_the_listed_form_holds_with_the_candidates_still_lis
     # placed for the hint)
     assert paths[4][0] == paths[3][0] + 1 and paths[4][1] == paths[3][1], paths
     assert paths[-1][1] <= 1 and paths[-1][0] >= steps - 2, paths
+
+
+def test_four_hundred_steps_through_the_one_call_equal_the_radix_select_path_and_the_oracle_at_the_end():
+    # a long decode loop in the steady state (the carried bound adapts from call to call): the one-call step and the
+    # separate calls through the radix select must leave the same counts, threshold, attention output and cache after
+    # every step, bit for bit; the oracle follows on metadata alone (its full sort per step is the slow part) and its
+    # selection is compared at the last steps.  No step may need the single-block fallback.
+    from harness import GpuLoop
+    w = ki.workload("llama", prefill=1500)                         # 256 segments, 384,000 entries, budget 12.5 %
+    steps = 400
+    per_seq = w.n_layers * w.n_kv_heads
+    c = ki.prefill_cache(w, reserve=1)
+    one = GpuLoop(w, c, w.budget, 1, steps * w.nseg, DEV, one_call=True, hint=[0, per_seq])
+    sep = GpuLoop(w, c, w.budget, 1, steps * w.nseg, DEV, fused=True)
+    hc = host_cache(w, c)
+    now = np.array([t - 1 for t in w.prefill], np.int32)
+    budget_np = np.array(list(w.budget), np.int64)
+    for step in range(steps):
+        inp = ki.decode_inputs(w, step)
+        now = now + 1
+        pos_new = np.repeat(now, per_seq).astype(np.int32)
+        d = {k: v.to(DEV) for k, v in inp.items()}
+        now_dev, pos_dev = torch.from_numpy(now).to(DEV), torch.from_numpy(pos_new).to(DEV)
+        a, b = one.step(d, now_dev, pos_dev), sep.step(d, now_dev, pos_dev)
+        assert torch.equal(one.kept, sep.kept) and torch.equal(one.thr, sep.thr), step
+        assert torch.equal(one.out, sep.out) and torch.equal(one.lse, sep.lse), step
+        n = int((a.seg_start[-1] + a.seg_len[-1]).item())
+        assert torch.equal(a.seg_start, b.seg_start) and torch.equal(a.seg_len, b.seg_len), step
+        if step % 50 == 49 or step == steps - 1:
+            assert torch.equal(a.pos[:n], b.pos[:n]) and torch.equal(a.log_beta[:n], b.log_beta[:n]), step
+            assert torch.equal(a.k[:n].view(torch.int16), b.k[:n].view(torch.int16)), step
+            assert torch.equal(a.v[:n].view(torch.int16), b.v[:n].view(torch.int16)), step
+        one.advance(a)
+        sep.advance(b)
+        # the oracle, on the last three steps only: its cache is brought there from the GPU's (already checked) state
+        if step == steps - 4:
+            hc = device_cache_to_host(w, a)
+        elif step > steps - 4:
+            oracle.append(hc, bf16_bits(inp["k_new"]), bf16_bits(inp["v_new"]), inp["log_beta_new"].numpy(), pos_new)
+            keep_ref, kept_ref, thr_ref = oracle.select(hc, oracle.score(hc, now), budget_np)
+            hc = oracle.compact(hc, keep_ref, a.cap, 1)
+            assert np.array_equal(one.kept.cpu().numpy(), kept_ref), step
+            assert np.array_equal(one.thr.cpu().numpy().view(np.uint32), thr_ref), step
+            assert compare_caches(device_cache_to_host(w, a), hc), step
+    assert kv.kvtrim_poll_error(one.ctx) == 0 and kv.kvtrim_poll_error(sep.ctx) == 0
+    listed, fallback = kv.kvtrim_select_path_counts(one.ctx)
+    assert (listed, fallback) == (steps - 1, 0)
