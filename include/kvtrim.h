@@ -278,11 +278,11 @@ kvtrim_status kvtrim_append(kvtrim_ctx *ctx, kvtrim_cache *c, const void *k_new,
  * required.  With a small evict_hint (see kvtrim_score_select) and up to 5 query heads per KV head (4 at head_dim
  * 64), at most 1024 segments per sequence, 1024 sequences and 16 new tokens per segment the step is THREE kernels:
  * one scores, lists the eviction candidates and - in each sequence's last block - ranks them, counts the evicted
- * entries per segment and leaves the destination's segment table, a destination offset for every chunk of 128
- * entries and the mask bytes of the few chunks that lose entries (further blocks of the same launch append the new
- * tokens); one moves every surviving row while using it for the attention of its segment (no mask pass, no
- * compaction scan: it writes the mask bytes of the chunks that lose nothing itself); one merges the partial
- * attention results.  Any other shape or hint runs the three calls one after the other.  Device-side errors as in
+ * entries per segment and per chunk of 128 entries and leaves the destination's segment table and, per segment, the
+ * indices of its evicted entries (further blocks of the same launch append the new tokens); one moves every
+ * surviving row while using it for the attention of its segment (no mask pass, no compaction scan: a block derives
+ * its chunk's destination from its segment's record and writes the chunk's mask bytes itself); one merges the
+ * partial attention results.  Any other shape or hint runs the three calls one after the other.  Device-side errors as in
  * the three calls. */
 kvtrim_status kvtrim_decode_step(kvtrim_ctx *ctx, kvtrim_cache *src, const void *k_new, const void *v_new,
                                  const float *log_beta_new, const float *log_tail_new, const int32_t *pos_new,

@@ -377,10 +377,11 @@ __device__ __forceinline__ void st_dev(T* p, T v) { __hip_atomic_store(p, v, __A
 // STEP (implies SCORE): the decode step in one call.  Every block scores a segment's new tokens from the new-token
 // buffers; one more block per segment, behind the scanning blocks of the grid, writes their rows and metadata into
 // the source cache and the segment's part of the row mover's chunk table.  The last block of a sequence also leaves
-// what the compaction needs: survivors per segment, the destination's segment table, a destination offset per chunk
-// of 128 entries (flagged when the chunk loses nothing) and the mask bytes - of the chunks that lose entries only
-// when the evicted entries are on the candidate list (their indices pass through LDS), of every entry after the
-// single-block select or with more evictions than the LDS list holds.
+// what the compaction needs: survivors per segment, the destination's segment table and - when the evicted entries
+// are on the candidate list - per chunk of 128 entries the number of entries it loses and per segment a record with
+// the start of its survivors in the destination and the indices of its evicted entries, from which a block of the
+// row mover places its chunk's survivors itself (and writes its mask bytes).  After the single-block select, or
+// with more evictions than the lists hold, it writes the whole mask and a destination offset per chunk instead.
 //
 // Cross-block traffic inside the kernel: the candidate lists, their counters, the lowest keys and the arrival
 // counters.  All of it is written with device-scope atomics or write-through stores whose acknowledgement the
@@ -399,7 +400,7 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
     __shared__ int s_last, s_ncand;
     __shared__ uint32_t s_base;
     // this block's candidates, before they go to the list; the last block of a sequence reuses the space (STEP)
-    __shared__ int32_t s_pool[(STEP ? 6 : 2) * FAST_STAGE];
+    __shared__ int32_t s_pool[(STEP ? 3 : 2) * FAST_STAGE];
     uint32_t* c_key = reinterpret_cast<uint32_t*>(s_pool);
     int32_t* c_pos = s_pool + FAST_STAGE;
     int32_t* c_idx = s_pool + (STEP ? 2 : 1) * FAST_STAGE;
@@ -622,6 +623,8 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
     int64_t cnt = 0;
     int64_t step_before = 0, step_total = 0;                      // STEP: destination entries before this sequence / of all sequences
     int step_chunks_before = 0;                                   // STEP: chunks of the sequences before this one
+    int my_len = 0;                                               // STEP: length of segment g0 + tid (one segment of the sequence per thread)
+    int32_t step_cex = 0, step_ctot = 0;                          // STEP: chunks of the sequence's segments before that one / of all of them
     if (STEP) {
         // entries per sequence of the whole batch (the destination of a sequence starts behind all earlier ones)
         for (int i = tid; i < sh.n_seq; i += FAST_THREADS) s_seqcnt[i] = 0;
@@ -632,7 +635,10 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
             const SegView v = seg_view<KIND>(c, g, sh.nseg, sa, &b2, &n2);
             if (v.len) atomicAdd(&s_seqcnt[g / sh.segs_per_seq], v.len);
             if (g < g0) chunks_before += (v.len + CMP_CHUNK - 1) / CMP_CHUNK;
-            if (g >= g0 && g < g0 + sh.segs_per_seq) kept_out[g] = 0;
+            if (g >= g0 && g < g0 + sh.segs_per_seq) {
+                kept_out[g] = 0;
+                s_pool[FAST_STAGE + (g - g0)] = v.len;            // (the staging space is free once the block has arrived)
+            }
         }
         step_chunks_before = block_sum<int32_t>(chunks_before, sm.lds32);
         int64_t need = 0;
@@ -648,6 +654,12 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
         __syncthreads();
         step_before = sm.before;
         step_total = tot;
+        // The per-chunk eviction counts of this sequence are cleared NOW, long before they are needed: the stores
+        // (write-through: the counts are added with device-scope atomics) complete while the candidates are ranked.
+        if (tid < sh.segs_per_seq) my_len = s_pool[FAST_STAGE + tid];
+        step_cex = block_excl_scan<int32_t>((my_len + CMP_CHUNK - 1) / CMP_CHUNK, sm.lds32, &step_ctot);
+        if (step_total <= sa.dst.cap)
+            for (int i = tid; i < step_ctot; i += FAST_THREADS) st_dev(&ws.step_chunk_ev[step_chunks_before + i], 0u);
         cnt = s_seqcnt[seq];
         __syncthreads();
     } else {
@@ -842,120 +854,70 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
             return;
         }
         const int nsg = sh.segs_per_seq;
-        // The evicted entries are among the listed ones unless the single-block select ran; they go through LDS,
-        // so there must not be too many (nothing retained at all also takes the other route).
+        // The evicted entries are among the listed ones unless the single-block select ran; they are handed over as
+        // lists, so there must not be too many (nothing retained at all also takes the other route).
         const bool sparse = out.mode == FSEL_ALL || (out.mode == FSEL_THRESHOLD && !used_fallback && k <= STEP_MAX_EVICT);
         int* s_cb = s_pool;                                       // first chunk of the segment, counted inside the sequence
-        int* s_len = s_pool + FAST_STAGE;
-        int* s_evl = s_pool + 2 * FAST_STAGE;                     // evicted entries (index in their segment), segment by segment
-        int* s_start = s_pool + 3 * FAST_STAGE;                   // the segment's first entry in the source
-        int* s_lossy_sl = s_pool + 4 * FAST_STAGE;                // the chunks that lose entries: segment, chunk in it
-        int* s_lossy_ch = s_pool + 5 * FAST_STAGE;
         uint32_t* s_fill = sm.h;                                  // fill counters of the scatter
-        uint32_t* s_dso = sm.h + STEP_MAX_SEGS;                   // the segment's destination, counted from the sequence's
+        const int32_t cex = step_cex, ctot = step_ctot;
+        uint32_t* chunk_ev = ws.step_chunk_ev + step_chunks_before;   // this sequence's chunks
         if (sparse) {
+            // What the row mover gets: per chunk the number of entries it loses (a byte; almost all 0), per segment a
+            // record - where its survivors start in the destination, and the indices of its evicted entries.  From
+            // these a block of the row mover places its chunk itself: survivors of chunk ch of segment g start at
+            // dst_start[g] + 128 ch - (evicted entries of g before the chunk).
             __syncthreads();
-            if (tid < nsg) s_ev[tid] = 0;
+            if (tid < nsg) {
+                s_ev[tid] = 0;
+                s_cb[tid] = cex;
+            }
             s_fill[tid] = 0;
-            if (tid == 0) sm.gather_n = 0;
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // the zeros written above are in place before any count is added
             __syncthreads();
             bool ev[FAST_ITEMS];
 #pragma unroll
             for (int u = 0; u < FAST_ITEMS; ++u) {
                 ev[u] = out.mode == FSEL_THRESHOLD && listed[u] && evicted_before(key[u], sg[u], ps[u], out.key_thr, out.seg_thr, out.pos_thr);
-                if (ev[u]) atomicAdd(&s_ev[sg[u] - g0], 1);
+                if (ev[u]) {
+                    const int sl = sg[u] - g0;
+                    atomicAdd(&s_ev[sl], 1);
+                    atomicAdd(&chunk_ev[s_cb[sl] + ix[u] / CMP_CHUNK], 1u);
+                }
             }
             __syncthreads();
-            int my_ev = 0, my_len = 0;                            // one segment per thread
-            int64_t my_start = 0;
-            if (tid < nsg) {
-                bool b2 = false, n2 = false;
-                const SegView v = seg_view<KIND>(c, g0 + tid, sh.nseg, sa, &b2, &n2);
-                my_len = v.len;
-                my_start = v.start;
-                my_ev = s_ev[tid];
-            }
-            int32_t etot, ctot;
+            const int my_ev = tid < nsg ? s_ev[tid] : 0;
+            int32_t etot;
             const int32_t eex = block_excl_scan<int32_t>(my_ev, sm.lds32, &etot);
-            const int32_t cex = block_excl_scan<int32_t>((my_len + CMP_CHUNK - 1) / CMP_CHUNK, sm.lds32, &ctot);
             int64_t ntot;
             const int64_t nex = block_excl_scan<int64_t>(tid < nsg ? (int64_t)(my_len - my_ev) + sa.reserve : 0, sm.lds64, &ntot);
             if (tid < nsg) {
                 const int g = g0 + tid;
                 s_off[tid] = eex;
-                s_cb[tid] = cex;
-                s_len[tid] = my_len;
-                s_start[tid] = (int)my_start;                     // (a context holds fewer than 2^31 entries)
-                s_dso[tid] = (uint32_t)nex;
                 kept_out[g] = my_len - my_ev;
                 sa.dst.seg_start[g] = step_before + nex;
                 sa.dst.seg_len[g] = my_len - my_ev;
+                StepSegRec* rec = ws.step_rec + g;
+                rec->dst_start = step_before + nex;
+                rec->cnt = my_ev;
+                rec->off = eex;
             }
             __syncthreads();
+            int32_t* evl = ws.step_evl + (size_t)seq * STEP_MAX_EVICT;
 #pragma unroll
             for (int u = 0; u < FAST_ITEMS; ++u) {
                 if (ev[u]) {
                     const int sl = sg[u] - g0;
-                    s_evl[s_off[sl] + (int)atomicAdd(&s_fill[sl], 1u)] = ix[u];
+                    const int slot = (int)atomicAdd(&s_fill[sl], 1u);
+                    evl[s_off[sl] + slot] = ix[u];
+                    if (slot < STEP_REC_IDX) ws.step_rec[g0 + sl].idx[slot] = ix[u];
                 }
-            }
-            __syncthreads();
-            // the chunks' destinations: neighbouring threads share a segment and take its chunks in turn
-            const int tps = nsg >= FAST_THREADS ? 1 : FAST_THREADS / nsg;
-            if (tid < nsg * tps) {
-                const int sl = tid / tps;
-                const int e0 = s_off[sl], ne = s_ev[sl], len_s = s_len[sl];
-                const int nch = (len_s + CMP_CHUNK - 1) / CMP_CHUNK;
-                int64_t* out_c = ws.cmp_chunk_dst + step_chunks_before + s_cb[sl];
-                const int64_t ds = step_before + (int64_t)s_dso[sl];
-                constexpr int EVR = 8;                            // the segment's first evicted entries stay in registers
-                int evr[EVR];
-#pragma unroll
-                for (int i = 0; i < EVR; ++i) evr[i] = i < ne ? s_evl[e0 + i] : 0x7fffffff;
-                for (int ch = tid % tps; ch < nch; ch += tps) {
-                    const int idx0 = ch * CMP_CHUNK;
-                    int before = 0, inside = 0;
-#pragma unroll
-                    for (int i = 0; i < EVR; ++i) {
-                        before += evr[i] < idx0;
-                        inside += evr[i] >= idx0 && evr[i] < idx0 + CMP_CHUNK;
-                    }
-                    for (int i = EVR; i < ne; ++i) {
-                        const int x = s_evl[e0 + i];
-                        before += x < idx0;
-                        inside += x >= idx0 && x < idx0 + CMP_CHUNK;
-                    }
-                    out_c[ch] = (ds + idx0 - before) | (inside == 0 ? CMP_DST_FULL : 0);
-                    if (inside) {
-                        const int slot = atomicAdd(&sm.gather_n, 1);   // (at most one per evicted entry)
-                        s_lossy_sl[slot] = sl;
-                        s_lossy_ch[slot] = ch;
-                    }
-                }
-            }
-            __syncthreads();
-            // the keep mask of the chunks that lose entries, 16 lanes per chunk and 8 entries per lane (the row mover
-            // writes the mask of the chunks that lose nothing)
-            const int nlossy = sm.gather_n;
-            for (int it = tid; it < nlossy * 16; it += FAST_THREADS) {
-                const int q = it >> 4, j0 = (it & 15) * 8;
-                const int sl = s_lossy_sl[q], idx0 = s_lossy_ch[q] * CMP_CHUNK;
-                const int e0 = s_off[sl], ne = s_ev[sl];
-                const int n = min(CMP_CHUNK, s_len[sl] - idx0);
-                unsigned gone = 0;                                // bit j: entry j0 + j of the chunk is evicted
-                for (int i = 0; i < ne; ++i) {
-                    const int x = s_evl[e0 + i] - idx0 - j0;
-                    if (x >= 0 && x < 8) gone |= 1u << x;
-                }
-                uint8_t* kp = sa.keep_out + (int64_t)s_start[sl] + idx0 + j0;
-#pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    if (j0 + j < n) kp[j] = !((gone >> j) & 1u);
             }
         } else {
             // after the single-block select (or with very many evictions) the evicted entries are not listed: one more
             // pass over the sequence leaves the keep mask and, per chunk of 128 entries, where its survivors go
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // (the zeros written earlier have landed)
             __syncthreads();
+            for (int i = tid; i < ctot; i += FAST_THREADS) st_dev(&chunk_ev[i], STEP_CHUNK_DENSE);   // "look at the mask and the table"
             int64_t cursor = step_before;
             int cb = step_chunks_before;
             const int lane = lane_id(), wave = tid >> 6;

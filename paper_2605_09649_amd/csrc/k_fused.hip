@@ -86,10 +86,12 @@ __device__ __forceinline__ float row16_sum(float x) {
 // index of `stage` instead, and k_cmp_unstage puts them in place after this kernel has ended.  Rows that do not move
 // are not written at all.
 // STEP (the one-call decode step, kvtrim_decode_step; out of place only): the tables come from the step's scoring
-// kernel instead of a compaction scan - the same per-chunk descriptors and destination offsets, and the keep mask
-// only where a chunk loses entries.  The kernel then also writes the keep mask of the chunks that lose nothing
-// (`keep` is the caller's output array) and commits the source segment's new length (step_seg_len = the source
-// cache's seg_len array; the new token was appended by the scoring kernel).
+// kernel instead of a compaction scan - the same per-chunk descriptors, but no destination per chunk: the number of
+// entries the chunk loses and a record per segment, from which the block derives where its survivors go and, in
+// the few chunks that lose entries, which they are.  The kernel then also writes the keep mask (`keep` is the
+// caller's output array) and commits the source segment's new length (step_seg_len = the source cache's seg_len
+// array; the new token was appended by the scoring kernel).  After the scoring kernel's single-block select the
+// per-chunk word says "dense": destination offsets and mask are in memory, as after a compaction scan.
 template <int D, int G, bool INPLACE, bool STEP = false>
 __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const uint8_t* keep,
                                                           CacheViewMut dst, CacheViewMut stage,
@@ -113,14 +115,42 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
     // descriptor and destination are fetched together with the two grid-wide words (the grid never exceeds the
     // tables; what they hold at or beyond `total` is not used)
     const ChunkDesc cd = ws.cmp_desc[ch];
-    const int64_t dflag = ws.cmp_chunk_dst[ch];
+    int64_t dflag = STEP ? 0 : ws.cmp_chunk_dst[ch];
+    const uint32_t step_ev = STEP ? ws.step_chunk_ev[ch] : 0u;    // STEP: entries the chunk loses (or "see the table")
     if (__hip_atomic_load(ws.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
     if (ch >= ws.cmp_chunk_prefix[sh.nseg]) return;
     const int64_t sbase = cd.first;
-    const int64_t dbase = dflag & ~CMP_DST_FULL;
+    // STEP: the scoring kernel leaves no destination per chunk (one block would write 16 K of them) but a record per
+    // SEGMENT - where the segment's survivors start and which of its entries go - from which the chunk's block
+    // places its survivors itself: they start at dst_start + (chunk's first index) - (evicted entries before it).
+    // Everything here is uniform over the block (scalar loads); the record is only needed for the stores and, in
+    // the few chunks that lose entries, for the survivor list.
+    const bool step_listed = STEP && step_ev != STEP_CHUNK_DENSE;
+    int step_idx0 = 0, step_cnt = 0, step_recw = 0;               // step_recw: lane l holds 32-bit word l of the segment's record
+    const int32_t* step_more = nullptr;                           // the segment's evicted entries beyond those in the record
+    int64_t dbase = dflag & ~CMP_DST_FULL;
+    if (STEP && !step_listed) {
+        dflag = ws.cmp_chunk_dst[ch];
+        dbase = dflag & ~CMP_DST_FULL;
+    }
+    // Called by whole wavefronts, for a full chunk AFTER its rows have been requested: the record comes with one
+    // vector load of 16 lanes - vector loads return in order, so the wait for the rows does not wait for it, whereas
+    // a scalar load would make every later scalar wait, and the row requests behind it, wait for the record.
+    auto step_place = [&]() {
+        static_assert(sizeof(StepSegRec) == 64 && STEP_REC_IDX == 12, "one word per lane: dst_start, cnt, off, twelve indices");
+        const int32_t* rw = reinterpret_cast<const int32_t*>(ws.step_rec + cd.seg);
+        step_recw = lane < 16 ? rw[lane] : 0;
+        step_idx0 = (int)(sbase - src.seg_start[cd.seg]);
+        step_cnt = __builtin_amdgcn_readlane(step_recw, 2);
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane(step_recw, 0), hi = (uint32_t)__builtin_amdgcn_readlane(step_recw, 1);
+        step_more = ws.step_evl + (size_t)(cd.seg / sh.segs_per_seq) * STEP_MAX_EVICT + __builtin_amdgcn_readlane(step_recw, 3);
+        int before = __popcll(__ballot(lane >= 4 && lane < 4 + min(step_cnt, STEP_REC_IDX) && step_recw < step_idx0));
+        for (int i = STEP_REC_IDX; i < step_cnt; ++i) before += step_more[i] < step_idx0;
+        dbase = (int64_t)(((uint64_t)hi << 32) | lo) + step_idx0 - before;
+    };
     // Every entry of the chunk survives (almost every chunk of a decode step): row r of the survivors is row r of
     // the chunk, so the rows are requested right away instead of after the mask has arrived and been ranked.
-    const bool full = (dflag & CMP_DST_FULL) != 0;                // uniform over the block
+    const bool full = step_listed ? step_ev == 0u : (dflag & CMP_DST_FULL) != 0;   // uniform over the block
     int cnt = 0;
     float md_lb = 0.f, md_lt = 0.f;
     int md_pos = 0, md_rank = tid;
@@ -137,8 +167,18 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
     } else {
         int rank = 0;
         bool flag = false;
+        if (step_listed) step_place();                            // (a chunk that loses entries needs the list first)
         if (tid < CMP_CHUNK) {
-            flag = tid < cd.n && keep[sbase + tid] != 0;
+            if (step_listed) {                                    // the mask of this chunk from the segment's list
+                flag = tid < cd.n;
+#pragma unroll
+                for (int i = 0; i < STEP_REC_IDX; ++i)
+                    flag = flag & !((i < step_cnt) & (__builtin_amdgcn_readlane(step_recw, 4 + i) == step_idx0 + tid));
+                for (int i = STEP_REC_IDX; i < step_cnt; ++i) flag = flag && step_more[i] != step_idx0 + tid;
+                if (tid < cd.n) const_cast<uint8_t*>(keep)[sbase + tid] = flag;
+            } else {
+                flag = tid < cd.n && keep[sbase + tid] != 0;
+            }
             const uint64_t mask = __ballot(flag);
             rank = mbcnt(mask);
             if (lane == 0) wave_cnt[wave] = __popcll(mask);
@@ -269,6 +309,7 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
             int srow[4];
             float qf[G][E];
             fetch(kk, vv, srow, qf);
+            if (step_listed && full) step_place();
             write_rows(kk, vv, srow);
             if (md_mine) write_metadata();                        // (wavefronts 0 and 1, which have rows whenever they have entries)
             if (attend) attend_rows(kk, vv, qf);

@@ -101,6 +101,9 @@ static Layout layout_of(const kvtrim_config* c, bool select_only) {
     l.off[32] = bump(cur, (size_t)c->n_seq * l.fl_cap * sizeof(int32_t));      // fl_idx
     l.off[33] = bump(cur, seg_tables * (size_t)nseg * sizeof(int32_t));        // step_len
     l.off[34] = bump(cur, l.max_att_chunks * 4 * sizeof(int32_t));             // att_pages
+    l.off[35] = bump(cur, seg_tables * (size_t)nseg * sizeof(StepSegRec));     // step_rec
+    l.off[36] = bump(cur, seg_tables * (size_t)c->n_seq * STEP_MAX_EVICT * sizeof(int32_t));   // step_evl
+    l.off[37] = bump(cur, (size_t)l.max_cmp_chunks * sizeof(uint32_t));        // step_chunk_ev
     l.total = (cur + 255) & ~(size_t)255;
     return l;
 }
@@ -143,6 +146,9 @@ static void bind(const Layout& l, char* b, Workspace& w) {
     w.fl_idx = (int32_t*)(b + l.off[32]);
     w.step_len = (int32_t*)(b + l.off[33]);
     w.att_pages = (int32_t*)(b + l.off[34]);
+    w.step_rec = (StepSegRec*)(b + l.off[35]);
+    w.step_evl = (int32_t*)(b + l.off[36]);
+    w.step_chunk_ev = (uint32_t*)(b + l.off[37]);
     w.fl_cap = l.fl_cap;
     w.max_sel_chunks = l.max_sel_chunks;
     w.max_cmp_chunks = l.max_cmp_chunks;

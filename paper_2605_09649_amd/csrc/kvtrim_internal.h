@@ -111,6 +111,16 @@ struct StepArgs {
 };
 
 constexpr int ATT_PAGE_FULL = 0x40000000;   // in ws.att_pages: the page has no empty slot
+// One-call decode step: per segment, where its survivors start in the destination and which of its entries go -
+// the first STEP_REC_IDX of them here, all of them in ws.step_evl from `off` on (index in the sequence's part).
+constexpr int STEP_REC_IDX = 12;
+struct alignas(64) StepSegRec {
+    int64_t dst_start;
+    int32_t cnt;
+    int32_t off;
+    int32_t idx[STEP_REC_IDX];
+};
+constexpr uint32_t STEP_CHUNK_DENSE = 0xFFFFFFFFu;
 constexpr int STEP_MAX_SEGS = 1024;  // segments per sequence the one-call decode step handles
 constexpr int STEP_MAX_EVICT = 1024; // evictions per sequence it lists (more: the keep mask and per-chunk offsets are written by one block)
 constexpr int STEP_MAX_SEQS = 1024;  // sequences it handles
@@ -176,6 +186,10 @@ struct Workspace {
     int32_t fl_cap;
     // one-call decode step
     int32_t* step_len;           // [nseg] segment lengths with the step's new tokens
+    StepSegRec* step_rec;        // [nseg] what the row mover needs of a segment to place a chunk's survivors
+    int32_t* step_evl;           // [n_seq][STEP_MAX_EVICT] the evicted entries (index in their segment), segment by segment
+    uint32_t* step_chunk_ev;     // [max_cmp_chunks] entries a chunk loses in this step (STEP_CHUNK_DENSE: look at the
+                                 // keep mask and ws.cmp_chunk_dst instead)
     int64_t max_sel_chunks, max_cmp_chunks, max_att_chunks;
 };
 
