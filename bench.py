@@ -392,6 +392,11 @@ class Runner:
         out, lse, scale = self.out, self.lse, self.scale
         if a.paged and s > 0:
             pc = self.pc
+            if not (a.separate_score_select or a.separate_calls or a.defrag_every):   # the whole step in one call
+                kv.kvtrim_paged_decode_step(ctx, pc, inp["k_new"], inp["v_new"], inp["log_beta_new"], self.pos_news[s], self.nows[s],
+                                            self.budget, self.score, self.keep, self.kept, inp["q"], 0, w.n_layers, scale, out, lse,
+                                            thr_key_out=self.thr, log_tail_new=inp.get("log_tail_new"), evict_hint=self.per_seq)
+                return
             kv.kvtrim_paged_append(ctx, pc, inp["k_new"], inp["v_new"], inp["log_beta_new"], self.pos_news[s],
                                    log_tail_new=inp.get("log_tail_new"))
             if a.separate_score_select:
@@ -465,7 +470,9 @@ def moved_bytes(w, a, n_cand, n_ret, rows_written_in_place=None):
     else:
         m["score_select"] = (8 + tail + 4 + 4 + 1) * n_cand        # one scoring pass (score out), one mask pass (score in, mask out)
     if a.paged:
-        m["evict"] = 5 * n_cand                                    # mask and position in (the few freed slots out)
+        if a.separate_score_select or a.separate_calls or a.defrag_every:
+            m["evict"] = 5 * n_cand                                # mask and position in (the few freed slots out)
+        # (in the one call the eviction rides in the mask kernel, which reads the positions anyway)
         m["attend"] = (4 * D + 4) * n_ret + 6 * D * nq             # K, V and position of every live slot; q in, out out
     elif a.inplace:
         per_ip = n_cand + R * n_ret + R * (rows_written_in_place or 0) + 6 * D * nq
@@ -659,7 +666,9 @@ def run_decode(args, brief=False):
           {"fused": "", "paged": "_paged", "inplace": "_inplace", "unfused": "_unfused"}[variant]
     one_call = not (args.paged or args.inplace or args.unfused or args.separate_score_select or args.separate_calls)
     calls = ("decode_step (append, stages 1-4 in one call; three kernels per decode step where the shape allows)" if one_call else
-             ("paged_append, " + ("paged_score, paged_select" if args.separate_score_select else "paged_score_select") +
+             ("paged_decode_step (append, score_select, evict, attn in one call; paged layout: no K/V moved)"
+              if not (args.separate_score_select or args.separate_calls or args.defrag_every) else
+              "paged_append, " + ("paged_score, paged_select" if args.separate_score_select else "paged_score_select") +
               ", paged_evict, paged_attn (paged layout: no K/V moved)") if args.paged else
              ("append, " + ("score, select_global" if args.separate_score_select else "score_select") + ", " +
               ("compact, decode_attn" if args.unfused and not args.inplace else

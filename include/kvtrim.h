@@ -391,6 +391,20 @@ kvtrim_status kvtrim_paged_score_select(kvtrim_ctx *ctx, const kvtrim_paged_cach
                                         const int64_t *budget, float *score_out, uint8_t *keep_out, int32_t *kept_out,
                                         uint32_t *thr_key_out, int64_t evict_hint, void *hip_stream);
 
+/* A decode step on the paged layout in one call: leaves in the pages, score_out, keep_out, kept_out, thr_key_out, out
+ * and lse exactly what
+ *     kvtrim_paged_append(one token per segment) -> kvtrim_paged_score_select(now, budget, evict_hint)
+ *     -> kvtrim_paged_evict(keep_out) -> kvtrim_paged_attn(q)
+ * leave there (arguments as in those four calls; one row per segment in the new-token arrays).  With a small
+ * evict_hint the mask kernel of the decode-step selection applies the eviction as it writes the mask, which saves
+ * the pass of kvtrim_paged_evict over all pages: seven kernels per step.  Any other hint runs the four calls. */
+kvtrim_status kvtrim_paged_decode_step(kvtrim_ctx *ctx, kvtrim_paged_cache *c, const void *k_new, const void *v_new,
+                                       const float *log_beta_new, const float *log_tail_new, const int32_t *pos_new,
+                                       const int32_t *now, const int64_t *budget, float *score_out, uint8_t *keep_out,
+                                       int32_t *kept_out, uint32_t *thr_key_out, const void *q, int32_t layer_begin,
+                                       int32_t layer_end, float softmax_scale, float *out, float *lse, int64_t evict_hint,
+                                       void *hip_stream);
+
 /* Stage 3 on the paged layout: live slots with keep[e] == 0 become empty; pages left without a
  * live entry return to the free list and leave their segment's block table.  No K/V moves. */
 kvtrim_status kvtrim_paged_evict(kvtrim_ctx *ctx, kvtrim_paged_cache *c, const uint8_t *keep, void *hip_stream);

@@ -10,7 +10,7 @@ from .binding import (PAGE_SIZE, Cache, Context, Gate, KvtrimError, PagedCache, 
                       kvtrim_gate_scratch_bytes, kvtrim_append, kvtrim_append_compact, kvtrim_compact,
                       kvtrim_compact_attn, kvtrim_compact_attn_inplace, kvtrim_compact_inplace, kvtrim_decode_attn, kvtrim_decode_attn_soft, kvtrim_kernel_name, kvtrim_min_room,
                       kvtrim_occupancy, kvtrim_paged_append, kvtrim_paged_attn, kvtrim_paged_build,
-                      kvtrim_paged_defrag, kvtrim_paged_evict, kvtrim_paged_score, kvtrim_paged_score_select, kvtrim_paged_select, kvtrim_poll_error,
+                      kvtrim_paged_defrag, kvtrim_paged_evict, kvtrim_paged_score, kvtrim_paged_score_select, kvtrim_paged_decode_step, kvtrim_paged_select, kvtrim_poll_error,
                       kvtrim_profile_begin, kvtrim_profile_end, kvtrim_score, kvtrim_select_global,
                       kvtrim_select_global_noalloc, kvtrim_score_select, kvtrim_select_path_counts, kvtrim_decode_step,
                       kvtrim_workspace_bytes, library_path, load_library)
@@ -20,7 +20,7 @@ __all__ = ["PAGE_SIZE", "Cache", "Context", "Gate", "KvtrimError", "PagedCache",
            "kvtrim_gate_scratch_bytes", "kvtrim_append", "kvtrim_append_compact", "kvtrim_compact",
            "kvtrim_compact_attn", "kvtrim_compact_attn_inplace", "kvtrim_compact_inplace", "kvtrim_decode_attn", "kvtrim_decode_attn_soft", "kvtrim_kernel_name", "kvtrim_min_room",
            "kvtrim_occupancy", "kvtrim_paged_append", "kvtrim_paged_attn", "kvtrim_paged_build",
-           "kvtrim_paged_defrag", "kvtrim_paged_evict", "kvtrim_paged_score", "kvtrim_paged_score_select", "kvtrim_paged_select", "kvtrim_poll_error",
+           "kvtrim_paged_defrag", "kvtrim_paged_evict", "kvtrim_paged_score", "kvtrim_paged_score_select", "kvtrim_paged_decode_step", "kvtrim_paged_select", "kvtrim_poll_error",
            "kvtrim_profile_begin", "kvtrim_profile_end", "kvtrim_score", "kvtrim_select_global",
            "kvtrim_select_global_noalloc", "kvtrim_score_select", "kvtrim_select_path_counts", "kvtrim_decode_step",
            "kvtrim_workspace_bytes", "library_path", "load_library"]

@@ -972,7 +972,10 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
 
 // keep[e] from the published triple; survivors per segment are added to kept_out (zeroed by k_fast_scan).
 // PAGED: the segment's slots through its block table; an empty slot's byte is 0.
-template <bool PAGED>
+// EVICT (PAGED only; the paged decode step in one call): stage 3 of the paged layout rides along - a live slot that
+// is not kept becomes empty (position -1), the live counts of its page and segment go down, and a page left without
+// a live entry is marked for release (owner -2), exactly as k_pg_evict does from the mask.
+template <bool PAGED, bool EVICT = false>
 __global__ __launch_bounds__(FAST_THREADS) void k_fast_mask(CacheView c, const float* __restrict__ score, Shape sh,
                                                             Workspace ws, int bps, uint8_t* __restrict__ keep,
                                                             int32_t* __restrict__ kept_out, PagedArgs pg) {
@@ -1010,8 +1013,9 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_mask(CacheView c, const f
 #pragma unroll
         for (int u = 0; u < FAST_BATCH; ++u) {
             const int j = j0 + u * bps * FAST_THREADS;
+            bool kf = false;
             if (j < len) {
-                bool kf = fs.mode == FSEL_ALL;
+                kf = fs.mode == FSEL_ALL;
                 if (fs.mode == FSEL_THRESHOLD) {
                     const uint32_t key = key_of_score(sv[u]);
                     kf = key > fs.key_thr;
@@ -1020,6 +1024,18 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_mask(CacheView c, const f
                 if (PAGED && pv[u] < 0) kf = false;
                 keep[at[u]] = kf;
                 n += kf;
+            }
+            if (EVICT) {
+                // a wavefront holds 64 consecutive slots of one page here (or none: a segment's slots come in whole pages)
+                const bool gone = j < len && pv[u] >= 0 && !kf;
+                const int n_gone = __popcll(__ballot(gone));
+                if (gone) pg.evict_pos[at[u]] = -1;
+                if (n_gone && lane_id() == 0) {
+                    const int page = (int)(at[u] / KVTRIM_PAGE_SIZE);
+                    const int left = atomicSub(&pg.evict_page_live[page], n_gone) - n_gone;
+                    atomicSub(&pg.evict_seg_live[seg], n_gone);
+                    if (left <= 0) pg.evict_page_owner[page] = -2;
+                }
             }
         }
     }
@@ -1050,7 +1066,7 @@ kvtrim_status launch_score_select(kvtrim_ctx* ctx, const CacheView& c, const int
 // walking every segment's slots through its block table.  The caller has checked that the hint fits the list.
 kvtrim_status launch_score_select_paged(kvtrim_ctx* ctx, const CacheView& pool, const PagedArgs& pg, const int32_t* now,
                                         const int64_t* budget, float* score, uint8_t* keep, int32_t* kept, uint32_t* thr,
-                                        hipStream_t st) {
+                                        hipStream_t st, bool evict) {
     const Shape& sh = ctx->shape;
     const Workspace& ws = ctx->ws;
     int64_t bps = pool.cap / ((int64_t)sh.nseg * FAST_ENTRIES_PER_BLOCK);
@@ -1061,7 +1077,10 @@ kvtrim_status launch_score_select_paged(kvtrim_ctx* ctx, const CacheView& pool, 
     { ProfScope prof(ctx, K_FAST_SCAN, st);
       hipLaunchKernelGGL((k_fast_scan<true, SCAN_PAGED>), grid, block, 0, st, pool, now, (const float*)nullptr, score, budget, sh, ws, (int)bps, kept, thr, sa); }
     { ProfScope prof(ctx, K_FAST_MASK, st);
-      hipLaunchKernelGGL(k_fast_mask<true>, grid, block, 0, st, pool, (const float*)score, sh, ws, (int)bps, keep, kept, pg); }
+      if (evict)
+          hipLaunchKernelGGL((k_fast_mask<true, true>), grid, block, 0, st, pool, (const float*)score, sh, ws, (int)bps, keep, kept, pg);
+      else
+          hipLaunchKernelGGL((k_fast_mask<true, false>), grid, block, 0, st, pool, (const float*)score, sh, ws, (int)bps, keep, kept, pg); }
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;
 }

@@ -1072,8 +1072,46 @@ kvtrim_status kvtrim_paged_score_select(kvtrim_ctx* ctx, const kvtrim_paged_cach
     pg.seg_live = c->seg_live;
     pg.n_pages = c->n_pages;
     pg.max_pps = c->max_pages_per_seg;
+    pg.evict_pos = pg.evict_seg_live = pg.evict_page_live = pg.evict_page_owner = nullptr;
     return launch_score_select_paged(ctx, pool_view(c), pg, now, budget, score_out, keep_out, kept_out, thr_key_out,
                                      (hipStream_t)hip_stream);
+}
+
+kvtrim_status kvtrim_paged_decode_step(kvtrim_ctx* ctx, kvtrim_paged_cache* c, const void* k_new, const void* v_new,
+                                       const float* log_beta_new, const float* log_tail_new, const int32_t* pos_new,
+                                       const int32_t* now, const int64_t* budget, float* score_out, uint8_t* keep_out,
+                                       int32_t* kept_out, uint32_t* thr_key_out, const void* q, int32_t layer_begin,
+                                       int32_t layer_end, float softmax_scale, float* out, float* lse, int64_t evict_hint,
+                                       void* hip_stream) {
+    kvtrim_status rc = kvtrim_paged_append(ctx, c, k_new, v_new, log_beta_new, log_tail_new, pos_new, 1, hip_stream);
+    if (rc != KVTRIM_OK) return rc;
+    if (evict_hint <= 0 || 8 * (evict_hint + 1) > (int64_t)ctx->ws.fl_cap) {
+        rc = kvtrim_paged_score_select(ctx, c, now, budget, score_out, keep_out, kept_out, thr_key_out, evict_hint, hip_stream);
+        if (rc != KVTRIM_OK) return rc;
+        rc = kvtrim_paged_evict(ctx, c, keep_out, hip_stream);
+        if (rc != KVTRIM_OK) return rc;
+    } else {
+        // the decode-step selection, whose mask kernel also applies the eviction; then the emptied pages leave the tables
+        if (!now || !budget || !score_out || !keep_out || !kept_out) return bad(ctx, "now / budget / score_out / keep_out / kept_out is NULL");
+        if ((((uintptr_t)score_out) & 15) || (((uintptr_t)keep_out) & 3)) return bad(ctx, "score_out not 16-byte or keep_out not 4-byte aligned");
+        hipStream_t st = (hipStream_t)hip_stream;
+        PagedArgs pg;
+        pg.block_table = c->block_table;
+        pg.seg_pages = c->seg_pages;
+        pg.seg_live = c->seg_live;
+        pg.n_pages = c->n_pages;
+        pg.max_pps = c->max_pages_per_seg;
+        pg.evict_pos = c->pos;
+        pg.evict_seg_live = c->seg_live;
+        pg.evict_page_live = c->page_live;
+        pg.evict_page_owner = c->page_owner;
+        rc = launch_score_select_paged(ctx, pool_view(c), pg, now, budget, score_out, keep_out, kept_out, thr_key_out, st, true);
+        if (rc != KVTRIM_OK) return rc;
+        ProfScope prof(ctx, K_PG_TIDY, st);
+        hipLaunchKernelGGL(k_pg_tidy, dim3(ctx->shape.nseg), dim3(256), 0, st, view_of(c), ctx->ws.err);
+        KVTRIM_HIP(ctx, hipGetLastError());
+    }
+    return kvtrim_paged_attn(ctx, c, q, layer_begin, layer_end, softmax_scale, out, lse, hip_stream);
 }
 
 kvtrim_status kvtrim_paged_evict(kvtrim_ctx* ctx, kvtrim_paged_cache* c, const uint8_t* keep, void* hip_stream) {

@@ -91,6 +91,11 @@ struct PagedArgs {
     const int32_t* seg_live;
     int32_t n_pages;
     int32_t max_pps;
+    // for the mask kernel that also evicts (the paged decode step in one call): what an eviction updates
+    int32_t* evict_pos;
+    int32_t* evict_seg_live;
+    int32_t* evict_page_live;
+    int32_t* evict_page_owner;
 };
 
 // The decode step in one call (kvtrim_decode_step): the tokens that enter the cache in this step (laid out as kvtrim_append takes them;
@@ -235,7 +240,7 @@ kvtrim_status launch_select(kvtrim_ctx*, const CacheView&, const float* score, c
 // carried bound, resolved by the last block of every sequence, and the mask pass.
 kvtrim_status launch_score_select_paged(kvtrim_ctx*, const CacheView& pool, const PagedArgs&, const int32_t* now,
                                         const int64_t* budget, float* score, uint8_t* keep, int32_t* kept, uint32_t* thr,
-                                        hipStream_t);
+                                        hipStream_t, bool evict = false);
 kvtrim_status launch_score_select(kvtrim_ctx*, const CacheView&, const int32_t* now, const int64_t* budget, float* score,
                                   uint8_t* keep, int32_t* kept, uint32_t* thr, int64_t evict_hint, hipStream_t);
 kvtrim_status launch_step_scan(kvtrim_ctx*, const CacheView&, const int32_t* now, const int64_t* budget, float* score,

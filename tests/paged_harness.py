@@ -137,12 +137,14 @@ def ties_overflow(w, hc, score_ref, live, thr_ref, budget_np):
 
 
 def run_paged_both(w, budgets, device="cuda:0", cache_dict=None, now0=None, n_pages=None, max_pps=None, horizon=1,
-                   tweak_new=None, defrag_at=(), hint=None):
+                   tweak_new=None, defrag_at=(), hint=None, one_call=False):
     """budgets: one per-sequence budget list per step; step 0 selects on the ragged prefill cache
     and builds the pages, the later steps run on the pages.  tweak_new(step, inputs) may edit the
     generated inputs of a step (used to plant ties).  In the steps listed in defrag_at the pages are
     defragmented between eviction and attention.  hint: None runs stages 1 and 2 on the pages as two calls,
-    a number runs kvtrim_paged_score_select with that evict_hint.  Returns one dict of findings per step."""
+    a number runs kvtrim_paged_score_select with that evict_hint.  one_call: the paged steps run
+    kvtrim_paged_decode_step (append, score_select, evict and attention in one call; hint required).  Returns one dict of
+    findings per step."""
     reserve = 1
     if cache_dict is None:
         cache_dict = ki.prefill_cache(w, reserve=reserve)
@@ -201,6 +203,24 @@ def run_paged_both(w, budgets, device="cuda:0", cache_dict=None, now0=None, n_pa
             res["score_equal"] = bool(np.array_equal(score[:hc.cap].cpu().numpy()[live].view(np.uint32),
                                                      score_ref[live].view(np.uint32)))
             res["keep_equal"] = bool(np.array_equal(keep[:hc.cap].cpu().numpy()[live], keep_ref[live]))
+        elif one_call:
+            pos_before = pc.pos.clone()
+            kv.kvtrim_paged_decode_step(ctx, pc, d["k_new"], d["v_new"], d["log_beta_new"], pos_dev, now_dev, budget_dev, score, keep,
+                                        kept, d["q"], 0, w.n_layers, scale, out, lse, thr_key_out=thr,
+                                        log_tail_new=d.get("log_tail_new"), evict_hint=hint)
+            res["status_select"] = kv.kvtrim_poll_error(ctx)
+            # the evicted slots are empty already: scores and mask are checked on the survivors (matched through their
+            # positions) and the mask on the slots that were live before the call and are empty after it
+            post = PagedHost(pc, rows=False)
+            idx, counts = post.ordered_slots()
+            kept_live = live & (keep_ref != 0)
+            same = np.array_equal(counts, kept_ref)
+            res["score_equal"] = bool(same and np.array_equal(score.cpu().numpy()[idx].view(np.uint32),
+                                                              score_ref[kept_live].view(np.uint32)))
+            gone = (pos_before.cpu().numpy().reshape(-1) >= 0) & (post.pos.reshape(-1) < 0)
+            n_gone_ref = int(live.sum()) - int(kept_ref.sum())
+            res["keep_equal"] = bool(same and np.all(keep.cpu().numpy()[idx] == 1) and not keep.cpu().numpy()[:gone.size][gone].any()
+                                     and n_gone_ref - w.nseg <= int(gone.sum()) <= n_gone_ref)
         else:
             kv.kvtrim_paged_append(ctx, pc, d["k_new"], d["v_new"], d["log_beta_new"], pos_dev,
                                    log_tail_new=d.get("log_tail_new"))
@@ -226,7 +246,8 @@ def run_paged_both(w, budgets, device="cuda:0", cache_dict=None, now0=None, n_pa
                              "tight": bool(np.array_equal(after.seg_pages, (after.seg_live + P - 1) // P)),
                              "live_unchanged": bool(np.array_equal(before.seg_live, after.seg_live)),
                              "free_gain": after.n_free - before.n_free}
-        kv.kvtrim_paged_attn(ctx, pc, d["q"], 0, w.n_layers, scale, out, lse)
+        if not (one_call and step > 0):
+            kv.kvtrim_paged_attn(ctx, pc, d["q"], 0, w.n_layers, scale, out, lse)
         res["status"] = kv.kvtrim_poll_error(ctx)
         res["kept_equal"] = bool(np.array_equal(kept.cpu().numpy(), kept_ref)
                                  and np.array_equal(thr.cpu().numpy().view(np.uint32), thr_ref))

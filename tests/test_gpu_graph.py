@@ -72,7 +72,11 @@ class Loop:
 
     def step(self, slot):
         i, ctx, w = self.inp[slot], self.ctx, self.w
-        if self.paged:
+        if self.paged and self.calls == "paged_decode_step":
+            kv.kvtrim_paged_decode_step(ctx, self.pc, i["k_new"], i["v_new"], i["log_beta_new"], self.pos[slot], self.now[slot],
+                                        self.budget, self.score, self.keep, self.kept, i["q"], 0, w.n_layers, self.scale,
+                                        self.out[slot], thr_key_out=self.thr, evict_hint=w.n_layers * w.n_kv_heads)
+        elif self.paged:
             kv.kvtrim_paged_append(ctx, self.pc, i["k_new"], i["v_new"], i["log_beta_new"], self.pos[slot])
             kv.kvtrim_paged_score(ctx, self.pc, self.now[slot], self.score)
             kv.kvtrim_paged_select(ctx, self.pc, self.score, self.budget, self.keep, self.kept, self.thr)
@@ -129,11 +133,11 @@ def same(a, b):
                               b[k].view(np.uint8) if b[k].dtype.kind == "f" else b[k]) for k in a) and a.keys() == b.keys()
 
 
-@pytest.mark.parametrize("paged", [False, True, "inplace", "score_select", "decode_step"])
+@pytest.mark.parametrize("paged", [False, True, "inplace", "score_select", "decode_step", "paged_decode_step"])
 def test_two_captured_steps_replayed_three_times_match_the_eager_loop(paged):
     w = ki.workload("tiny", prefill=900)
-    calls = paged if paged in ("score_select", "decode_step") else "four"
-    inplace, paged = paged == "inplace", paged is True
+    calls = paged if paged in ("score_select", "decode_step", "paged_decode_step") else "four"
+    inplace, paged = paged == "inplace", paged is True or paged == "paged_decode_step"
     eager, graphed = Loop(w, paged, inplace, calls), Loop(w, paged, inplace, calls)
     for loop in (eager, graphed):
         loop.first_step()

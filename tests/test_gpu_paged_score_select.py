@@ -137,3 +137,82 @@ def test_bad_page_tables_are_reported():
     for hint in (0, 2):
         kv.kvtrim_paged_score_select(ctx, pc, now, budget, score, mask, kept, None, evict_hint=hint)
         assert kv.kvtrim_poll_error(ctx) == -6, hint
+
+
+# ---------------------------------------------------------------------------------- the paged step in one call
+
+@pytest.mark.parametrize("hint", [0, 16])
+def test_one_call_tiny_workload_paged_loop(hint):
+    w = ki.workload("tiny")
+    res = run_paged_both(w, [w.budget] * 14, device=DEV, hint=hint, one_call=True)
+    check(res)
+    listed, fallback = res[-1]["path_counts"]
+    assert (listed, fallback) == ((13, 0) if hint else (0, 0))
+
+
+@pytest.mark.parametrize("name,prefill,steps", [("llama", 700, 5), ("long", 900, 5), ("vlm", 640, 5), ("multiturn", 600, 4)])
+def test_one_call_scaled_down_workloads_paged(name, prefill, steps):
+    w = ki.workload(name, prefill=prefill)
+    check(run_paged_both(w, [w.budget] * steps, device=DEV, hint=w.n_layers * w.n_kv_heads, one_call=True))
+
+
+@pytest.mark.parametrize("hint", [4, 60])
+@pytest.mark.parametrize("S,L,H,G,D", [(1, 2, 2, 1, 128), (2, 2, 1, 7, 128), (3, 1, 2, 3, 64)])
+def test_one_call_ragged_segments_with_empty_ones_paged(S, L, H, G, D, hint):
+    w = wl(S, L, H, G, D)
+    rng = np.random.default_rng(S * 1000 + G * 10 + D)
+    seg_len = rng.integers(0, 20000, w.nseg)
+    seg_len[rng.integers(0, w.nseg)] = 0
+    seg_len[rng.integers(0, w.nseg)] = 5 * P
+    c, now = ki.ragged_cache(w, seg_len, reserve=1, salt=G)
+    per_seq = [int(seg_len[s * L * H:(s + 1) * L * H].sum()) for s in range(S)]
+    budget = [max(1, n // 3) for n in per_seq]
+    check(run_paged_both(w, [budget] * 5, device=DEV, cache_dict=c, now0=now.numpy(), hint=hint, one_call=True))
+
+
+def test_one_call_pages_are_freed_and_taken_again():
+    # whole pages empty out under the eviction that rides in the mask kernel, leave the block tables and are taken again
+    w = wl(1, 2, 3, 2, 64)
+    seg_len = [700, 130, 0, 1024, 255, 256]
+    c, now = ki.ragged_cache(w, seg_len, reserve=1, salt=11)
+    total = sum(seg_len)
+    budgets = [[total], [total - 6], [total - 12], [total - 18]] + [[total - 18 - 40 * i] for i in range(1, 40)]
+    budgets += [[10 ** 6]] * 10 + [[400]] * 6 + [[3], [0], [10 ** 6], [10 ** 6]]
+    res = run_paged_both(w, budgets, device=DEV, cache_dict=c, now0=now.numpy(), n_pages=40, hint=60, one_call=True)
+    check(res)
+    pages = [r["pages_in_use"] for r in res]
+    listed, fallback = res[-1]["path_counts"]
+    # (pages empty out - entirely at the budget of zero - and every segment takes one again afterwards)
+    assert min(pages) == 0 and pages[-1] == w.nseg and max(pages[:44]) > min(pages[44:60]) and listed >= 30, (pages, listed, fallback)
+
+
+@pytest.mark.parametrize("horizon", [2, 0])
+def test_one_call_lookahead_horizon_paged(horizon):
+    w = ki.workload("tiny", prefill=700)
+    check(run_paged_both(w, [w.budget] * 5, device=DEV, horizon=horizon, hint=16, one_call=True))
+
+
+def test_one_call_ties_at_the_threshold():
+    w = wl(2, 2, 2, 2, 64)
+    seg_len = [600, 300, 257, 900, 128, 0, 640, 1000]
+    c, now = ki.ragged_cache(w, seg_len, reserve=1, salt=5)
+    g = torch.Generator().manual_seed(1)
+    lb = c["log_beta"]
+    lb[torch.rand(lb.shape, generator=g) < 0.8] = 0.0
+
+    def plant(step, inp):
+        if step % 2 == 0:
+            inp["log_beta_new"][:] = 0.0
+
+    budgets = [[1500, 1200], [1490, 1190], [1480, 1180], [901, 600], [890, 590], [451, 100], [445, 99], [7, 98], [7, 98]]
+    res = run_paged_both(w, budgets, device=DEV, cache_dict=c, now0=now.numpy(), tweak_new=plant, hint=12, one_call=True)
+    check(res)
+    assert sum(r["ties_overflow"] for r in res[1:]) >= 5
+
+
+def test_one_call_budget_zero_and_above_full_per_sequence():
+    w = wl(3, 1, 2, 2, 128)
+    seg_len = [300, 200, 500, 1, 129, 640]
+    c, now = ki.ragged_cache(w, seg_len, reserve=1, salt=2)
+    budgets = [[400, 10 ** 6, 600], [0, 10 ** 6, 300], [5, 0, 10 ** 6], [10 ** 6, 10 ** 6, 0], [10 ** 6, 3, 2]]
+    check(run_paged_both(w, budgets, device=DEV, cache_dict=c, now0=now.numpy(), hint=4, one_call=True))
