@@ -102,7 +102,8 @@ typedef struct {
 kvtrim_status kvtrim_create(kvtrim_ctx **out, const kvtrim_config *cfg);
 kvtrim_status kvtrim_destroy(kvtrim_ctx *ctx);
 size_t kvtrim_workspace_bytes(const kvtrim_config *cfg);
-const char *kvtrim_last_error(const kvtrim_ctx *ctx); /* host string, owned by ctx */
+const char *kvtrim_last_error(const kvtrim_ctx *ctx); /* host string, owned by ctx; ctx = NULL: why the calling
+                                                         thread's last kvtrim_create failed */
 
 /* Outside the hot loop: waits for `hip_stream`, then returns and clears the
  * sticky device flag (KVTRIM_OK, KVTRIM_ECAP, KVTRIM_EMISMATCH or KVTRIM_ELAYOUT). */

@@ -253,7 +253,7 @@ class Context:
         h = C.c_void_p()
         rc = lib.kvtrim_create(C.byref(h), C.byref(cfg))
         if rc != 0:
-            raise KvtrimError(rc, "kvtrim_create")
+            raise KvtrimError(rc, (lib.kvtrim_last_error(None) or b"kvtrim_create").decode())
         self.handle = h
 
     def close(self):

@@ -42,7 +42,7 @@ __device__ __forceinline__ void block_sum_n(int64_t (&v)[N], int64_t* lds /* [16
 // they are and there is no capacity to check.
 __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_prefix(CacheView src, const int32_t* __restrict__ kept,
                                                              CacheViewMut dst, int reserve, int align, Shape sh,
-                                                             Workspace ws, int inplace, int run) {
+                                                             Workspace ws, int inplace, int run, int gat) {
     __shared__ int64_t lds64[17];
     __shared__ int s_bad_layout, s_bad_kept;
     const int tid = threadIdx.x, nseg = sh.nseg;
@@ -61,7 +61,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_prefix(CacheView src, cons
             if (kp < 0 || kp > len) s_bad_kept = 1;
             nch = len > 0 ? ((int64_t)len + CMP_CHUNK - 1) / CMP_CHUNK : 0;
             need = ((int64_t)kp + reserve + align - 1) / align * align;
-            nrun = run > 0 && len > 0 ? ((int64_t)len + run - 1) / run : 0;
+            nrun = run > 0 && len > 0 ? ((int64_t)(gat ? kp : len) + run - 1) / run : 0;
         }
         int64_t tot_c, tot_e;
         const int64_t ex_c = block_excl_scan<int64_t>(nch, lds64, &tot_c);
@@ -105,10 +105,11 @@ template <bool PRE>
 __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const uint8_t* __restrict__ keep,
                                                            const int32_t* __restrict__ kept, CacheViewMut dst,
                                                            int reserve, int align, Shape sh, Workspace ws, int inplace,
-                                                           int run) {
+                                                           int run, int gat) {
     __shared__ int64_t lds64[17];
     __shared__ int64_t lds_n[16 * 8];
     __shared__ int s_cnt[SCAN_THREADS];
+    __shared__ int s_ex[SCAN_THREADS];
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int g = blockIdx.x;
     const int nseg = sh.nseg;
@@ -127,7 +128,13 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const 
     int o_len = 0, o_kp = 0;                                      // !PRE: table entry of segment `tid`
     int64_t o_st = 0;
     if (PRE) {
-        if (__hip_atomic_load(ws.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
+        // One decision for the whole block: another block of this launch may raise the flag (a mask that disagrees
+        // with `kept`) between the reads of two wavefronts, and a block that lost some of its wavefronts would scan
+        // counts that were never written.
+        __shared__ int s_err;
+        if (tid == 0) s_err = __hip_atomic_load(ws.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (s_err != 0) return;
         chunks_before = ws.cmp_chunk_prefix[g];
         dst_before = dst.seg_start[g];
         if (run > 0) runs_before = ws.att_chunk_prefix[g];
@@ -173,7 +180,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const 
             acc[5] |= (o_kp < 0 || o_kp > o_len);
             const int64_t nc = o_len > 0 ? ((int64_t)o_len + CMP_CHUNK - 1) / CMP_CHUNK : 0;
             const int64_t need = ((int64_t)o_kp + reserve + align - 1) / align * align;   // align = 1 unless pages are built
-            const int64_t nrun = run > 0 && o_len > 0 ? ((int64_t)o_len + run - 1) / run : 0;
+            const int64_t nrun = run > 0 && o_len > 0 ? ((int64_t)(gat ? o_kp : o_len) + run - 1) / run : 0;
             acc[3] += nc;
             acc[2] += need;
             acc[7] += nrun;
@@ -203,12 +210,17 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const 
     }
 
     const int cbase = (int)chunks_before;
+    int64_t gat_slots = 0;                                        // gat: slots of this segment in ws.gat_src
     if (run > 0) {                                                // the segment's runs, for the loop-shaped fused kernel
-        const int nrun = len > 0 ? (int)(((int64_t)len + run - 1) / run) : 0;
+        // (gat: the runs are chunks of the DESTINATION segment, for the gathering fused kernel)
+        const int rlen = gat ? (own_ok ? kept[g] : 0) : len;
+        const int64_t rstart = gat ? dst_before : start;
+        const int nrun = len > 0 && rlen > 0 ? (int)(((int64_t)rlen + run - 1) / run) : 0;
+        if (gat) gat_slots = (int64_t)nrun * CMP_CHUNK;
         for (int u = tid; u < nrun; u += SCAN_THREADS) {
             ChunkDesc d;
-            d.first = start + (int64_t)u * run;
-            d.n = min(run, len - u * run);
+            d.first = rstart + (int64_t)u * run;
+            d.n = min(run, rlen - u * run);
             d.seg = g;
             ws.att_desc[runs_before + u] = d;
         }
@@ -243,9 +255,34 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const 
             d.seg = g;
             ws.cmp_desc[cbase + ch] = d;
         }
+        if (gat) {
+            // the source row of every destination row, in slots of CMP_CHUNK per destination chunk (the segment's
+            // chunks are consecutive, so row r of the segment has slot runs_before * CMP_CHUNK + r): a wavefront per
+            // source chunk ranks its survivors again (the mask bytes come from the cache this time)
+            s_ex[tid] = (int)(running + ex);
+            __syncthreads();
+            int32_t* slots = ws.gat_src + runs_before * CMP_CHUNK;
+            for (int c0 = wave; c0 < tile_n; c0 += (SCAN_THREADS / 64) * SCAN_BATCH) {
+                request(tile0, tile_n, c0);
+#pragma unroll
+                for (int u = 0; u < SCAN_BATCH; ++u) {
+                    const int cl = c0 + u * (SCAN_THREADS / 64);
+                    if (cl >= tile_n) break;                      // uniform over the wavefront
+                    const uint64_t m0 = __ballot(b[u][0] != 0), m1 = __ballot(b[u][1] != 0);
+                    const int r0 = s_ex[cl] + mbcnt(m0), r1 = s_ex[cl] + __popcll(m0) + mbcnt(m1);
+                    const int32_t row = (int32_t)(start + (int64_t)(tile0 + cl) * CMP_CHUNK + lane);
+                    // (a mask with more survivors than `kept` says - reported below - must not leave the segment's slots)
+                    if (b[u][0] != 0 && r0 >= 0 && r0 < gat_slots) slots[r0] = row;
+                    if (b[u][1] != 0 && r1 >= 0 && r1 < gat_slots) slots[r1] = row + 64;
+                }
+            }
+        }
         running += tot;
     }
-    if (run > 0) {
+    if (gat) {
+        // the slots behind the segment's last row, up to the end of its last chunk, name a row that exists
+        for (int64_t r = running + tid; r < gat_slots; r += SCAN_THREADS) ws.gat_src[runs_before * CMP_CHUNK + r] = (int32_t)start;
+    } else if (run > 0) {
         // per run: where its survivors go, and whether every one of its chunks is full (the chunk entries above
         // were written by other threads of this block)
         __syncthreads();
@@ -439,15 +476,17 @@ __global__ __launch_bounds__(GAT_WAVES * 64) void k_cmp_gather(CacheView src, co
 }
 
 void launch_cmp_scan_aligned(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const int32_t* kept,
-                             const CacheViewMut& dst, int32_t reserve, int32_t align, int32_t run, hipStream_t st) {
+                             const CacheViewMut& dst, int32_t reserve, int32_t align, int32_t run, hipStream_t st,
+                             bool gat) {
     ProfScope prof(ctx, K_CMP_SCAN, st);
+    const int g = gat ? 1 : 0;
     if (ctx->shape.nseg > 1024) {                                 // see k_cmp_prefix
-        hipLaunchKernelGGL(k_cmp_prefix, dim3(1), dim3(SCAN_THREADS), 0, st, src, kept, dst, reserve, align, ctx->shape, ctx->ws, 0, run);
+        hipLaunchKernelGGL(k_cmp_prefix, dim3(1), dim3(SCAN_THREADS), 0, st, src, kept, dst, reserve, align, ctx->shape, ctx->ws, 0, run, g);
         hipLaunchKernelGGL(k_cmp_scan<true>, dim3(ctx->shape.nseg), dim3(SCAN_THREADS), 0, st, src, keep, kept, dst, reserve,
-                           align, ctx->shape, ctx->ws, 0, run);
+                           align, ctx->shape, ctx->ws, 0, run, g);
     } else {
         hipLaunchKernelGGL(k_cmp_scan<false>, dim3(ctx->shape.nseg), dim3(SCAN_THREADS), 0, st, src, keep, kept, dst, reserve,
-                           align, ctx->shape, ctx->ws, 0, run);
+                           align, ctx->shape, ctx->ws, 0, run, g);
     }
 }
 
@@ -460,12 +499,12 @@ void launch_cmp_scan_inplace(kvtrim_ctx* ctx, const CacheViewMut& c, const uint8
     src.k = c.k; src.v = c.v; src.log_beta = c.log_beta; src.pos = c.pos;
     src.seg_start = c.seg_start; src.seg_len = c.seg_len; src.cap = c.cap; src.log_tail = c.log_tail;
     if (ctx->shape.nseg > 1024) {
-        hipLaunchKernelGGL(k_cmp_prefix, dim3(1), dim3(SCAN_THREADS), 0, st, src, kept, c, 0, 1, ctx->shape, ctx->ws, 1, run);
+        hipLaunchKernelGGL(k_cmp_prefix, dim3(1), dim3(SCAN_THREADS), 0, st, src, kept, c, 0, 1, ctx->shape, ctx->ws, 1, run, 0);
         hipLaunchKernelGGL(k_cmp_scan<true>, dim3(ctx->shape.nseg), dim3(SCAN_THREADS), 0, st, src, keep, kept, c, 0, 1,
-                           ctx->shape, ctx->ws, 1, run);
+                           ctx->shape, ctx->ws, 1, run, 0);
     } else {
         hipLaunchKernelGGL(k_cmp_scan<false>, dim3(ctx->shape.nseg), dim3(SCAN_THREADS), 0, st, src, keep, kept, c, 0, 1,
-                           ctx->shape, ctx->ws, 1, run);
+                           ctx->shape, ctx->ws, 1, run, 0);
     }
 }
 

@@ -92,13 +92,19 @@ __device__ __forceinline__ float row16_sum(float x) {
 // caller's output array) and commits the source segment's new length (step_seg_len = the source cache's seg_len
 // array; the new token was appended by the scoring kernel).  After the scoring kernel's single-block select the
 // per-chunk word says "dense": destination offsets and mask are in memory, as after a compaction scan.
-template <int D, int G, bool INPLACE, bool STEP = false>
+// GATHER (a selection that keeps few entries of every chunk - the first eviction after a long prefill; out of place
+// only): a block per 128-row chunk of the DESTINATION.  The compaction scan has listed the chunks (ws.att_desc) and
+// the source row of every destination row (ws.gat_src, 128 slots per chunk, the slots behind a ragged chunk's last
+// row naming a live row), so a block asks for its row numbers at once, together with its descriptor, and for the
+// rows as soon as the numbers are there; neither the mask nor the source's chunk table is read.
+template <int D, int G, bool INPLACE, bool STEP = false, bool GATHER = false>
 __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const uint8_t* keep,
                                                           CacheViewMut dst, CacheViewMut stage,
                                                           const uint16_t* __restrict__ q,
                                                           Shape sh, Workspace ws, float scale_log2,
                                                           int layer_begin, int layer_end, int32_t* step_seg_len = nullptr) {
     static_assert(!(STEP && INPLACE), "the one-call step compacts out of place");
+    static_assert(!(GATHER && (INPLACE || STEP)), "the gathering instance compacts out of place, from a keep mask");
     typedef Row<D> R;
     typedef typename R::vec vec;
     constexpr int E = R::E;
@@ -114,12 +120,21 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
     const int ch = blockIdx.x;
     // descriptor and destination are fetched together with the two grid-wide words (the grid never exceeds the
     // tables; what they hold at or beyond `total` is not used)
-    const ChunkDesc cd = ws.cmp_desc[ch];
-    int64_t dflag = STEP ? 0 : ws.cmp_chunk_dst[ch];
+    const ChunkDesc cd = GATHER ? ws.att_desc[ch] : ws.cmp_desc[ch];
+    int64_t dflag = STEP ? 0 : (GATHER ? CMP_DST_FULL : ws.cmp_chunk_dst[ch]);
     const uint32_t step_ev = STEP ? ws.step_chunk_ev[ch] : 0u;    // STEP: entries the chunk loses (or "see the table")
+    // GATHER: the source rows of this thread's rows (the slots exist for every block of the grid; what they hold at
+    // or beyond the last chunk is not used)
+    int gat_row[4] = {0, 0, 0, 0}, gat_md = 0;
+    if (GATHER) {
+        const int32_t* slots = ws.gat_src + (int64_t)ch * CMP_CHUNK;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) gat_row[u] = slots[(tid >> 6) * CMP_WAVE_ROWS + u * 4 + ((tid & 63) >> 4)];
+        if (tid < CMP_CHUNK) gat_md = slots[tid];
+    }
     if (__hip_atomic_load(ws.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
-    if (ch >= ws.cmp_chunk_prefix[sh.nseg]) return;
-    const int64_t sbase = cd.first;
+    if (ch >= (GATHER ? ws.att_chunk_prefix : ws.cmp_chunk_prefix)[sh.nseg]) return;
+    const int64_t sbase = GATHER ? 0 : cd.first;                  // (GATHER: row numbers are absolute)
     // STEP: the scoring kernel leaves no destination per chunk (one block would write 16 K of them) but a record per
     // SEGMENT - where the segment's survivors start and which of its entries go - from which the chunk's block
     // places its survivors itself: they start at dst_start + (chunk's first index) - (evicted entries before it).
@@ -128,7 +143,7 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
     const bool step_listed = STEP && step_ev != STEP_CHUNK_DENSE;
     int step_idx0 = 0, step_cnt = 0, step_recw = 0;               // step_recw: lane l holds 32-bit word l of the segment's record
     const int32_t* step_more = nullptr;                           // the segment's evicted entries beyond those in the record
-    int64_t dbase = dflag & ~CMP_DST_FULL;
+    int64_t dbase = GATHER ? cd.first : dflag & ~CMP_DST_FULL;
     if (STEP && !step_listed) {
         dflag = ws.cmp_chunk_dst[ch];
         dbase = dflag & ~CMP_DST_FULL;
@@ -159,9 +174,10 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
     if (full) {
         cnt = cd.n;
         if (md_mine) {
-            md_lb = src.log_beta[sbase + tid];
-            if (src.log_tail) md_lt = src.log_tail[sbase + tid];
-            md_pos = src.pos[sbase + tid];
+            const int64_t e = GATHER ? (int64_t)gat_md : sbase + tid;
+            md_lb = src.log_beta[e];
+            if (src.log_tail) md_lt = src.log_tail[e];
+            md_pos = src.pos[e];
         }
         if (STEP && tid < cd.n) const_cast<uint8_t*>(keep)[sbase + tid] = 1;   // (chunks that lose entries have their mask already)
     } else {
@@ -233,7 +249,7 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int r = min(r0 + u * 4 + sub, cnt - 1);         // clamped: loads stay on live rows
-            srow[u] = full ? r : list[r];                         // the chunk entry the row comes from
+            srow[u] = GATHER ? gat_row[u] : (full ? r : list[r]); // the chunk entry the row comes from
             const int64_t se = (sbase + srow[u]) * VPR + col;
             kk[u] = R::ld(sk + se);
             vv[u] = R::ld(sv + se);
@@ -413,6 +429,18 @@ static bool dispatch_fused(int G, dim3 grid, hipStream_t st, const CacheView& sr
         KVTRIM_CASE(1) KVTRIM_CASE(2) KVTRIM_CASE(3) KVTRIM_CASE(4) KVTRIM_CASE(5) KVTRIM_CASE(6)
 #undef KVTRIM_CASE
         default: return false;                                    // larger groups take the loop-shaped kernel (k_att_fused)
+    }
+}
+
+template <int D>
+static bool dispatch_gather(int G, dim3 grid, hipStream_t st, const CacheView& src, const CacheViewMut& dst,
+                            const uint16_t* q, const Shape& sh, const Workspace& ws, float scale_log2, int lb, int le) {
+    switch (G) {
+#define KVTRIM_CASE(g) \
+    case g: hipLaunchKernelGGL((k_cmp_attn<D, g, false, false, true>), grid, dim3(FUS_THREADS), 0, st, src, nullptr, dst, dst, q, sh, ws, scale_log2, lb, le); return true;
+        KVTRIM_CASE(1) KVTRIM_CASE(2) KVTRIM_CASE(3) KVTRIM_CASE(4) KVTRIM_CASE(5)
+#undef KVTRIM_CASE
+        default: return false;
     }
 }
 
@@ -604,12 +632,28 @@ kvtrim_status launch_compact_attn(kvtrim_ctx* ctx, const CacheView& src, const u
         if (!launch_attn_fused(ctx, src, keep, dst, q, layer_begin, layer_end, scale, st)) return KVTRIM_EINVAL;
         return launch_combine(ctx, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, st);
     }
+    const int64_t dst_chunks = dst.cap / CMP_CHUNK + sh.nseg;    // upper bound on the destination's chunks
+    if (sparse && alu_fits && dst_chunks <= ws.max_att_chunks && dst_chunks * CMP_CHUNK <= ws.gat_slots &&
+        max_chunks <= ws.max_cmp_chunks) {
+        // Few survivors per source chunk: the fused kernel's gathering instance, a block per chunk of the destination
+        // (a block per source chunk would write one partial result per 128 source entries for a handful of survivors
+        // each).  The compaction scan lists the destination's chunks and the source row of each of their rows.
+        launch_cmp_scan_aligned(ctx, src, keep, kept, dst, reserve, 1, CMP_CHUNK, st, true);
+        bool ok;
+        {
+            ProfScope prof(ctx, K_CMP_ATTN, st);
+            const float scale_log2 = scale * 1.4426950408889634f;
+            ok = sh.head_dim == 128
+                     ? dispatch_gather<128>(sh.group, dim3((unsigned)dst_chunks), st, src, dst, q, sh, ws, scale_log2, layer_begin, layer_end)
+                     : dispatch_gather<64>(sh.group, dim3((unsigned)dst_chunks), st, src, dst, q, sh, ws, scale_log2, layer_begin, layer_end);
+        }
+        if (!ok) return KVTRIM_EINVAL;
+        return launch_combine(ctx, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, st);
+    }
     if (max_chunks > ws.max_att_chunks || sparse || !alu_fits) {
         // Run the two stages one after the other, which computes the same thing: when there are too many source
-        // chunks for the partial-result buffer, and when the destination is so much smaller than the source that
-        // few rows can survive (the first eviction after a long prefill: a fused kernel would launch one block and
-        // write one partial result per 128 source entries for a handful of survivors each - measured 5.4 ms
-        // against 3.0 ms for the two calls at 1 survivor in 16).
+        // chunks for the partial-result buffer, for groups of query heads the one-shot kernel does not serve, and
+        // for a sparse selection the gathering instance cannot take.
         kvtrim_status rc = launch_compact(ctx, src, keep, kept, dst, reserve, st);
         if (rc != KVTRIM_OK) return rc;
         CacheView d;

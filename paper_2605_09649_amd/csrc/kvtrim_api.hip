@@ -36,7 +36,7 @@ struct Layout {
     size_t off[40];
     int32_t fl_cap;
     size_t total;
-    int64_t max_sel_chunks, max_cmp_chunks, max_att_chunks;
+    int64_t max_sel_chunks, max_cmp_chunks, max_att_chunks, gat_slots;
 };
 
 static size_t bump(size_t& cur, size_t bytes) {
@@ -104,6 +104,9 @@ static Layout layout_of(const kvtrim_config* c, bool select_only) {
     l.off[35] = bump(cur, seg_tables * (size_t)nseg * sizeof(StepSegRec));     // step_rec
     l.off[36] = bump(cur, seg_tables * (size_t)c->n_seq * STEP_MAX_EVICT * sizeof(int32_t));   // step_evl
     l.off[37] = bump(cur, (size_t)l.max_cmp_chunks * sizeof(uint32_t));        // step_chunk_ev
+    // a destination under a quarter of the source: at most max_entries / 4 rows in chunks of CMP_CHUNK, one ragged chunk per segment
+    l.gat_slots = select_only ? 0 : c->max_entries / 4 + ((int64_t)nseg + 1) * CMP_CHUNK;
+    l.off[38] = bump(cur, (size_t)l.gat_slots * sizeof(int32_t));              // gat_src
     l.total = (cur + 255) & ~(size_t)255;
     return l;
 }
@@ -149,6 +152,8 @@ static void bind(const Layout& l, char* b, Workspace& w) {
     w.step_rec = (StepSegRec*)(b + l.off[35]);
     w.step_evl = (int32_t*)(b + l.off[36]);
     w.step_chunk_ev = (uint32_t*)(b + l.off[37]);
+    w.gat_src = (int32_t*)(b + l.off[38]);
+    w.gat_slots = l.gat_slots;
     w.fl_cap = l.fl_cap;
     w.max_sel_chunks = l.max_sel_chunks;
     w.max_cmp_chunks = l.max_cmp_chunks;
@@ -220,12 +225,21 @@ size_t kvtrim_workspace_bytes(const kvtrim_config* cfg) {
     return layout_of(cfg, false).total;
 }
 
+// Why the calling thread's last kvtrim_create failed (there is no context to hold the text).
+static thread_local char g_create_error[256] = "no context";
+
 kvtrim_status kvtrim_create(kvtrim_ctx** out, const kvtrim_config* cfg) {
     if (!out) return KVTRIM_EINVAL;
     *out = nullptr;
-    if (!config_ok(cfg)) return KVTRIM_EINVAL;
+    if (!config_ok(cfg)) {
+        snprintf(g_create_error, sizeof g_create_error, "kvtrim_create: configuration out of range");
+        return KVTRIM_EINVAL;
+    }
     kvtrim_ctx* ctx = new (std::nothrow) kvtrim_ctx;
-    if (!ctx) return KVTRIM_ENOMEM;
+    if (!ctx) {
+        snprintf(g_create_error, sizeof g_create_error, "kvtrim_create: no host memory for the context");
+        return KVTRIM_ENOMEM;
+    }
     memset(ctx, 0, sizeof(*ctx));
     ctx->cfg = *cfg;
     shape_of(cfg, ctx->shape);
@@ -236,15 +250,26 @@ kvtrim_status kvtrim_create(kvtrim_ctx** out, const kvtrim_config* cfg) {
     }
     const Layout l = layout_of(cfg, false);
     ctx->ws_bytes = l.total;
-    if (hipGetDevice(&ctx->device) != hipSuccess || hipMalloc(&ctx->ws_base, l.total) != hipSuccess) {
+    hipError_t e = hipGetDevice(&ctx->device);
+    if (e != hipSuccess) {
+        snprintf(g_create_error, sizeof g_create_error, "kvtrim_create: hipGetDevice: %s", hipGetErrorString(e));
         (void)hipGetLastError();
         delete ctx;
-        return KVTRIM_ENOMEM;
+        return KVTRIM_EHIP;
     }
-    if (hipHostMalloc((void**)&ctx->err_host, sizeof(int32_t), hipHostMallocDefault) != hipSuccess ||
-        hipMemset(ctx->ws_base, 0, l.total) != hipSuccess ||
-        hipMemset((char*)ctx->ws_base + l.off[25], 0xFF, (size_t)cfg->n_seq * 16 * sizeof(uint32_t)) != hipSuccess ||   // fast_min: "no key seen"
-        hipDeviceSynchronize() != hipSuccess) {
+    e = hipMalloc(&ctx->ws_base, l.total);
+    if (e != hipSuccess) {                                        // (an earlier asynchronous failure is reported here too)
+        snprintf(g_create_error, sizeof g_create_error, "kvtrim_create: hipMalloc of the %zu-byte workspace: %s", l.total,
+                 hipGetErrorString(e));
+        (void)hipGetLastError();
+        delete ctx;
+        return e == hipErrorOutOfMemory ? KVTRIM_ENOMEM : KVTRIM_EHIP;
+    }
+    if ((e = hipHostMalloc((void**)&ctx->err_host, sizeof(int32_t), hipHostMallocDefault)) != hipSuccess ||
+        (e = hipMemset(ctx->ws_base, 0, l.total)) != hipSuccess ||
+        (e = hipMemset((char*)ctx->ws_base + l.off[25], 0xFF, (size_t)cfg->n_seq * 16 * sizeof(uint32_t))) != hipSuccess ||   // fast_min: "no key seen"
+        (e = hipDeviceSynchronize()) != hipSuccess) {
+        snprintf(g_create_error, sizeof g_create_error, "kvtrim_create: setting up the workspace: %s", hipGetErrorString(e));
         (void)hipGetLastError();
         if (ctx->err_host) (void)hipHostFree(ctx->err_host);
         (void)hipFree(ctx->ws_base);
@@ -328,7 +353,7 @@ kvtrim_status kvtrim_destroy(kvtrim_ctx* ctx) {
     return KVTRIM_OK;
 }
 
-const char* kvtrim_last_error(const kvtrim_ctx* ctx) { return ctx ? ctx->last_error : "no context"; }
+const char* kvtrim_last_error(const kvtrim_ctx* ctx) { return ctx ? ctx->last_error : g_create_error; }
 
 kvtrim_status kvtrim_poll_error(kvtrim_ctx* ctx, void* hip_stream) {
     if (!ctx) return KVTRIM_EINVAL;

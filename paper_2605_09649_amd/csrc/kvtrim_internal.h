@@ -195,6 +195,10 @@ struct Workspace {
     int32_t* step_evl;           // [n_seq][STEP_MAX_EVICT] the evicted entries (index in their segment), segment by segment
     uint32_t* step_chunk_ev;     // [max_cmp_chunks] entries a chunk loses in this step (STEP_CHUNK_DENSE: look at the
                                  // keep mask and ws.cmp_chunk_dst instead)
+    // gathering fused kernel (sparse selections): the source row of every destination row, CMP_CHUNK slots per
+    // destination chunk, written by the compaction scan
+    int32_t* gat_src;            // [gat_slots]
+    int64_t gat_slots;
     int64_t max_sel_chunks, max_cmp_chunks, max_att_chunks;
 };
 
@@ -264,8 +268,11 @@ kvtrim_status launch_attn_paged(kvtrim_ctx*, const CacheView& pool, const int32_
                                 hipStream_t);
 // run > 0: also writes the table of `run`-entry runs of all segments that the loop-shaped fused kernel reads
 // (ws.att_chunk_prefix / ws.att_desc), so that no separate plan kernel is needed.
+// gat: the runs are CMP_CHUNK-row chunks of the DESTINATION segments (run = CMP_CHUNK), and ws.gat_src gets the source
+// row of every destination row - what the gathering instance of the fused kernel reads.
 void launch_cmp_scan_aligned(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const int32_t* kept,
-                             const CacheViewMut& dst, int32_t reserve, int32_t align, int32_t run, hipStream_t);
+                             const CacheViewMut& dst, int32_t reserve, int32_t align, int32_t run, hipStream_t,
+                             bool gat = false);
 kvtrim_status launch_cmp_copy(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const CacheViewMut& dst,
                               hipStream_t);
 kvtrim_status launch_occupancy(kvtrim_ctx*, const CacheView&, const int32_t* now, double* occ, hipStream_t);

@@ -281,6 +281,67 @@ def test_sparse_selection_takes_the_wavefront_per_chunk_mover(D, horizon):
     assert compare_caches(device_cache_to_host(w, dst), dst_ref)
 
 
+@pytest.mark.parametrize("G,D,horizon,many", [(4, 128, 1, False), (1, 128, 2, False), (5, 128, 1, False), (3, 128, 1, True),
+                                              (2, 64, 1, False), (4, 64, 2, False)])
+def test_sparse_selection_in_the_fused_call_gathers_by_destination_chunk(G, D, horizon, many):
+    # compaction + attention in one call with a destination under a quarter of the source and a group of query heads
+    # the one-shot kernel serves: its gathering instance runs, a block per 128-row chunk of the DESTINATION reading the
+    # source rows the compaction scan has listed.  One entry in sixteen survives on average; some source chunks keep
+    # nothing, some everything, one segment is empty, one keeps nothing, one keeps exactly one chunk's worth, segments
+    # end in ragged chunks; `many`: more than 1024 segments (the scan's prefix kernel).  Layers [1, 3) attend.
+    w = wl(2, 180 if many else 3, 3, G, D)
+    rng = np.random.default_rng(1000 + 16 * G + D + horizon)
+    seg_len = rng.integers(1, 700 if many else 6000, w.nseg)
+    seg_len[3] = 0
+    seg_len[5] = 128 * 9 + 1
+    seg_len[7] = 300
+    seg_len[9] = 128 * 20
+    c, _ = ki.ragged_cache(w, seg_len, salt=35)
+    c = ki.with_horizon(c, horizon)
+    hc = host_cache(w, c)
+    keep_np = (rng.random(hc.cap) < 1.0 / 16).astype(np.uint8)
+    s5, s7, s9 = int(hc.seg_start[5]), int(hc.seg_start[7]), int(hc.seg_start[9])
+    keep_np[s5 + 128:s5 + 3 * 128] = 1                            # two source chunks that keep everything
+    keep_np[s5 + 4 * 128:s5 + 6 * 128] = 0                        # two that keep nothing
+    keep_np[s5 + 9 * 128] = 1                                     # the one-entry tail chunk
+    keep_np[s7:s7 + 300] = 0                                      # a segment that keeps nothing
+    keep_np[s9:s9 + 128 * 20] = 0
+    keep_np[s9 + 5:s9 + 128 * 20:20] = 1                          # exactly 128 survivors: one full destination chunk
+    kept_np = np.array([keep_np[s:s + n].sum() for s, n in zip(hc.seg_start, hc.seg_len)], np.int32)
+    assert kept_np[7] == 0 and kept_np[9] == 128
+    dst_cap = int(kept_np.sum()) + 2 * w.nseg
+    assert dst_cap < hc.cap // 4
+    dst_ref = oracle.compact(hc, keep_np, dst_cap, 2)
+    q = ki.decode_inputs(w, 3)["q"]
+    scale = 1.0 / math.sqrt(D)
+    ref, ref_lse = oracle.attend(dst_ref, bf16_bits(q), scale)
+    ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, D, hc.cap)
+    dst = kv.Cache.empty(w.nseg, D, dst_cap, DEV, with_tail=horizon != 1)
+    out = torch.full(ref.shape, 99.0, dtype=torch.float32, device=DEV)
+    lse = torch.full(ref_lse.shape, 99.0, dtype=torch.float32, device=DEV)
+    keep_d, kept_d = torch.from_numpy(keep_np).to(DEV), torch.from_numpy(kept_np).to(DEV)
+    kv.kvtrim_profile_begin(ctx, (1 << kv.binding.N_KERNELS) - 1)
+    kv.kvtrim_compact_attn(ctx, kv.Cache.from_dict(c, DEV), keep_d, kept_d, dst, 2, q.to(DEV), 1, 3, scale, out, lse)
+    times = kv.kvtrim_profile_end(ctx)
+    assert kv.kvtrim_poll_error(ctx) == 0
+    assert times["k_cmp_attn"][1] == 1 and "k_cmp_copy" not in times      # the fused kernel ran, not the two stages
+    assert compare_caches(device_cache_to_host(w, dst), dst_ref)
+    o = out.cpu().numpy()
+    assert np.all(o[:, 0] == 99.0)
+    assert attn_error(o[:, 1:3], ref[:, 1:3]) <= ATTN_TOL
+    fin = np.isfinite(ref_lse[:, 1:3])
+    assert np.abs(lse.cpu().numpy()[:, 1:3][fin] - ref_lse[:, 1:3][fin]).max() <= 2e-3
+    assert np.all(np.isneginf(lse.cpu().numpy()[:, 1:3][~fin]))
+    # a mask with more survivors than `kept` says is reported (as that, not as a failed HIP call)
+    keep_bad = keep_np.copy()
+    keep_bad[s7:s7 + 300] = 1
+    guard = kv.Cache.empty(w.nseg, D, dst_cap, DEV, with_tail=horizon != 1)
+    kv.kvtrim_compact_attn(ctx, kv.Cache.from_dict(c, DEV), torch.from_numpy(keep_bad).to(DEV), kept_d, guard, 2, q.to(DEV),
+                           1, 3, scale, out, lse)
+    assert kv.kvtrim_poll_error(ctx) == -5                         # KVTRIM_EMISMATCH
+    assert kv.kvtrim_poll_error(ctx) == 0
+
+
 # ---------------------------------------------------------------------------------- degenerate budgets, ties
 
 def run_select_compact(w, c, now, budget, score_override=None, reserve=1):
