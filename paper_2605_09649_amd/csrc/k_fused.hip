@@ -30,6 +30,12 @@ constexpr int FUS_THREADS = CMP_THREADS;
 
 typedef unsigned v4u __attribute__((ext_vector_type(4)));
 typedef unsigned v2u __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// acc + a.lo * b.lo + a.hi * b.hi on a pair of packed bf16 values (products and sum in fp32)
+__device__ __forceinline__ float dot2_bf16(unsigned a, unsigned b, float acc) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), acc, false);
+}
 
 template <int D>
 struct Row;
@@ -51,6 +57,10 @@ struct Row<128> {
         f[4] = __uint_as_float(x.z << 16); f[5] = __uint_as_float(x.z & 0xffff0000u);
         f[6] = __uint_as_float(x.w << 16); f[7] = __uint_as_float(x.w & 0xffff0000u);
     }
+    static __device__ __forceinline__ unsigned word(vec x, int w) { return w == 0 ? x.x : (w == 1 ? x.y : (w == 2 ? x.z : x.w)); }
+    static __device__ __forceinline__ float dot(vec a, vec b) {   // the lane's 8-element slice of q . k
+        return dot2_bf16(a.w, b.w, dot2_bf16(a.z, b.z, dot2_bf16(a.y, b.y, dot2_bf16(a.x, b.x, 0.f))));
+    }
 };
 template <>
 struct Row<64> {
@@ -68,6 +78,8 @@ struct Row<64> {
         f[0] = __uint_as_float(x.x << 16); f[1] = __uint_as_float(x.x & 0xffff0000u);
         f[2] = __uint_as_float(x.y << 16); f[3] = __uint_as_float(x.y & 0xffff0000u);
     }
+    static __device__ __forceinline__ unsigned word(vec x, int w) { return w == 0 ? x.x : x.y; }
+    static __device__ __forceinline__ float dot(vec a, vec b) { return dot2_bf16(a.y, b.y, dot2_bf16(a.x, b.x, 0.f)); }
 };
 
 // sum over the 16 lanes of a row group, result in every lane
@@ -110,11 +122,10 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
     constexpr int E = R::E;
     constexpr int VPR = 16;                                       // lanes (vectors) per row
     constexpr int NW = FUS_THREADS / 64;                          // 8 wavefronts
-    constexpr int MW = NW / 2;                                    // wavefronts merged through LDS at a time
     __shared__ int wave_cnt[CMP_CHUNK / 64];
     __shared__ int list[CMP_CHUNK];
     __shared__ float s_m[NW][G], s_l[NW][G];
-    __shared__ float s_o[MW][G][D];
+    __shared__ float s_o[NW][G][D];
 
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int ch = blockIdx.x;
@@ -233,19 +244,10 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
     const int r0 = wave * CMP_WAVE_ROWS;                          // this wavefront's rows of the survivor list
     const bool has_rows = r0 < cnt;                               // uniform over the wavefront
 
-    float o[G][E], m[G], l[G];
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-        m[g] = -INFINITY;
-        l[g] = 0.f;
-#pragma unroll
-        for (int e = 0; e < E; ++e) o[g][e] = 0.f;
-    }
-
     const vec* sk = reinterpret_cast<const vec*>(src.k);
     const vec* sv = reinterpret_cast<const vec*>(src.v);
     // the three steps of a wavefront that has rows: fetch rows and queries, write the rows out, attend
-    auto fetch = [&](vec (&kk)[4], vec (&vv)[4], int (&srow)[4], float (&qf)[G][E]) {
+    auto fetch = [&](vec (&kk)[4], vec (&vv)[4], int (&srow)[4], vec (&qp)[G]) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int r = min(r0 + u * 4 + sub, cnt - 1);         // clamped: loads stay on live rows
@@ -257,7 +259,7 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
         if (attend) {
             const int64_t hq0 = ((int64_t)seq * sh.n_layers + layer) * sh.n_q_heads + (int64_t)head * G;
 #pragma unroll
-            for (int g = 0; g < G; ++g) R::unpack(reinterpret_cast<const vec*>(q + (hq0 + g) * D)[col], qf[g]);
+            for (int g = 0; g < G; ++g) qp[g] = reinterpret_cast<const vec*>(q + (hq0 + g) * D)[col];   // (stays packed: q.k is a packed dot product)
         }
     };
     auto write_rows = [&](const vec (&kk)[4], const vec (&vv)[4], const int (&srow)[4]) {
@@ -281,40 +283,58 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
             t.pos[de] = md_pos;
         }
     };
-    auto attend_rows = [&](const vec (&kk)[4], const vec (&vv)[4], const float (&qf)[G][E]) {
-        float z[4][G];
+    // Attention of this wavefront's 16 rows, one query head at a time from q.k to the partial result: each 16-lane row
+    // group takes a softmax partial over its 4 rows, the four row groups are merged with lane shuffles, and the
+    // wavefront's partial for the head goes to LDS at once, so that the accumulators of one head are alive at a time,
+    // not those of all G (74 instead of 84-115 registers at G = 4, head_dim 128: three blocks per compute unit
+    // instead of two; the in-place instance went from 277 to 239 us at the long-context workload).
+    auto attend_rows = [&](const vec (&kk)[4], const vec (&vv)[4], const vec (&qp)[G]) {
+        bool valid[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            float kf[E];
-            R::unpack(kk[u], kf);
-            const bool valid = r0 + u * 4 + sub < cnt;
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                float part = 0.f;
-#pragma unroll
-                for (int e = 0; e < E; ++e) part = fmaf(qf[g][e], kf[e], part);
-                const float s = row16_sum(part);
-                z[u][g] = valid ? s * scale_log2 : -INFINITY;
-            }
-        }
-        float vf[4][E];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) R::unpack(vv[u], vf[u]);
+        for (int u = 0; u < 4; ++u) valid[u] = r0 + u * 4 + sub < cnt;
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            const float mx = fmaxf(fmaxf(z[0][g], z[1][g]), fmaxf(z[2][g], z[3][g]));
-            const float m_safe = mx == -INFINITY ? 0.f : mx;
+            float z[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float s = row16_sum(R::dot(qp[g], kk[u]));
+                z[u] = valid[u] ? s * scale_log2 : -INFINITY;
+            }
+            const float mx = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
+            float m_all = fmaxf(mx, __shfl_xor(mx, 16, 64));
+            m_all = fmaxf(m_all, __shfl_xor(m_all, 32, 64));      // maximum over the wavefront's 16 rows
+            const float m_fin = m_all == -INFINITY ? 0.f : m_all;
             float p[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) p[u] = __builtin_amdgcn_exp2f(z[u][g] - m_safe);
-            l[g] = (p[0] + p[1]) + (p[2] + p[3]);
-            m[g] = mx;
+            for (int u = 0; u < 4; ++u) p[u] = __builtin_amdgcn_exp2f(z[u] - m_fin);
+            float l_all = (p[0] + p[1]) + (p[2] + p[3]);
+            l_all += __shfl_xor(l_all, 16, 64);
+            l_all += __shfl_xor(l_all, 32, 64);
+            float og[E];
 #pragma unroll
-            for (int e = 0; e < E; ++e) {
-                float acc = p[0] * vf[0][e];
+            for (int w = 0; w < E / 2; ++w) {                     // V is unpacked a 32-bit word (two columns) at a time
+                float a = 0.f, b = 0.f;
 #pragma unroll
-                for (int u = 1; u < 4; ++u) acc = fmaf(p[u], vf[u][e], acc);
-                o[g][e] = acc;
+                for (int u = 0; u < 4; ++u) {
+                    unsigned x = R::word(vv[u], w);
+                    asm volatile("" : "+v"(x));                   // (unpacked again for every head: kept unpacked, V costs 2 E registers more)
+                    a = fmaf(p[u], __uint_as_float(x << 16), a);
+                    b = fmaf(p[u], __uint_as_float(x & 0xffff0000u), b);
+                }
+                a += __shfl_xor(a, 16, 64);
+                a += __shfl_xor(a, 32, 64);
+                b += __shfl_xor(b, 16, 64);
+                b += __shfl_xor(b, 32, 64);
+                og[2 * w] = a;
+                og[2 * w + 1] = b;
+            }
+            if (sub == 0) {
+#pragma unroll
+                for (int e = 0; e < E; ++e) s_o[wave][g][col * E + e] = og[e];
+            }
+            if (lane == 0) {
+                s_m[wave][g] = m_all;
+                s_l[wave][g] = l_all;
             }
         }
     };
@@ -323,18 +343,18 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
         if (has_rows) {
             vec kk[4], vv[4];
             int srow[4];
-            float qf[G][E];
-            fetch(kk, vv, srow, qf);
+            vec qp[G];
+            fetch(kk, vv, srow, qp);
             if (step_listed && full) step_place();
             write_rows(kk, vv, srow);
             if (md_mine) write_metadata();                        // (wavefronts 0 and 1, which have rows whenever they have entries)
-            if (attend) attend_rows(kk, vv, qf);
+            if (attend) attend_rows(kk, vv, qp);
         }
     } else {
         vec kk[4], vv[4];
         int srow[4];
-        float qf[G][E];
-        if (has_rows) fetch(kk, vv, srow, qf);
+        vec qp[G];
+        if (has_rows) fetch(kk, vv, srow, qp);
         if (moves) {
             // every wavefront of the block holds its rows and metadata in registers before any of them overwrites an entry
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -343,73 +363,30 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
         }
         if (has_rows) {
             if (moves) write_rows(kk, vv, srow);
-            if (attend) attend_rows(kk, vv, qf);
+            if (attend) attend_rows(kk, vv, qp);
         }
     }
     if (!attend) return;
 
-    // merge the four row groups of the wavefront (lanes xor 16, xor 32) ...
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-        float m_all = fmaxf(m[g], __shfl_xor(m[g], 16, 64));
-        m_all = fmaxf(m_all, __shfl_xor(m_all, 32, 64));
-        const float m_fin = m_all == -INFINITY ? 0.f : m_all;
-        const float wgt = __builtin_amdgcn_exp2f(m[g] - m_fin);
-        float l_all = l[g] * wgt;
-        l_all += __shfl_xor(l_all, 16, 64);
-        l_all += __shfl_xor(l_all, 32, 64);
-#pragma unroll
-        for (int e = 0; e < E; ++e) {
-            float x = o[g][e] * wgt;
-            x += __shfl_xor(x, 16, 64);
-            x += __shfl_xor(x, 32, 64);
-            o[g][e] = x;
-        }
-        m[g] = m_all;
-        l[g] = l_all;
-        if (lane == 0) {
-            s_m[wave][g] = m_all;
-            s_l[wave][g] = l_all;
-        }
-    }
-    // ... then the wavefronts of the block: the upper half hands its sums to the lower half
-    // through LDS, the lower half adds its own and publishes, and all threads reduce.
-    if (wave >= MW && sub == 0) {
-#pragma unroll
-        for (int g = 0; g < G; ++g)
-#pragma unroll
-            for (int e = 0; e < E; ++e) s_o[wave - MW][g][col * E + e] = o[g][e];
-    }
+    // the partials of the wavefronts that had rows are merged by all threads
     __syncthreads();
-    if (wave < MW && sub == 0) {
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            const float mo = s_m[wave + MW][g];
-            const float mn = fmaxf(m[g], mo);
-            const float ms = mn == -INFINITY ? 0.f : mn;
-            const float wa = __builtin_amdgcn_exp2f(m[g] - ms), wb = __builtin_amdgcn_exp2f(mo - ms);
-#pragma unroll
-            for (int e = 0; e < E; ++e) s_o[wave][g][col * E + e] = o[g][e] * wa + s_o[wave][g][col * E + e] * wb;
-            if (col == 0) {
-                s_l[wave][g] = l[g] * wa + s_l[wave + MW][g] * wb;
-                s_m[wave][g] = mn;
-            }
-        }
-    }
-    __syncthreads();
+    const int nw = min(NW, (cnt + CMP_WAVE_ROWS - 1) / CMP_WAVE_ROWS);
     float* part = ws.att_partial + (size_t)ch * G * (D + 2);
     for (int idx = tid; idx < G * D; idx += FUS_THREADS) {
         const int g = idx / D, d = idx % D;
         float M = -INFINITY;
 #pragma unroll
-        for (int s = 0; s < MW; ++s) M = fmaxf(M, s_m[s][g]);
+        for (int s = 0; s < NW; ++s)
+            if (s < nw) M = fmaxf(M, s_m[s][g]);
         const float Ms = M == -INFINITY ? 0.f : M;
         float accd = 0.f, lsum = 0.f;
 #pragma unroll
-        for (int s = 0; s < MW; ++s) {
-            const float w = __builtin_amdgcn_exp2f(s_m[s][g] - Ms);
-            accd += s_o[s][g][d] * w;
-            lsum += s_l[s][g] * w;
+        for (int s = 0; s < NW; ++s) {
+            if (s < nw) {
+                const float w = __builtin_amdgcn_exp2f(s_m[s][g] - Ms);
+                accd += s_o[s][g][d] * w;
+                lsum += s_l[s][g] * w;
+            }
         }
         part[g * (D + 2) + 2 + d] = accd;
         if (d == 0) {
