@@ -564,7 +564,7 @@ def run_decode(args, brief=False):
             log(f"[bench]   first step: {name:<18s} {1e3 * kms / n:7.1f} us x {n}")
 
     # ---- timed region: exactly K steps; the dominant kernels are bracketed by HIP events on the launch stream
-    mask = (1 << 8) | (1 << 10) | (1 << 13) | (1 << 30)   # k_cmp_copy, k_att_partial, k_cmp_attn, k_att_fused
+    mask = (1 << 8) | (1 << 10) | (1 << 13)   # k_cmp_copy, k_att_partial, k_cmp_attn
     if args.kernel_times:
         mask = all_kernels                    # every kernel (the events then add to the step time)
     kv.kvtrim_profile_begin(ctx, mask)
@@ -638,8 +638,6 @@ def run_decode(args, brief=False):
         if args.inplace:
             dom_bytes = [v for k, v in moved.items() if k.startswith("compact_attn")][0]
             stage_model_bytes = None
-    if dom not in prof and "k_att_fused" in prof:   # large groups of query heads: the loop-shaped fused kernel, same bytes
-        dom = "k_att_fused"
     if dom not in prof:                       # the cache is too large for the fused kernel: the library ran the two stages
         dom, dom_bytes, stage_model_bytes = "k_cmp_copy", alg["compact"], None
     dom_ms, dom_n = prof[dom]

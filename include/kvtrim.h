@@ -210,11 +210,13 @@ kvtrim_status kvtrim_occupancy(kvtrim_ctx *ctx, const kvtrim_cache *c, const int
 /* Stages 3 + 4 fused: exactly kvtrim_compact(src -> dst) followed by
  * kvtrim_decode_attn(dst), with the same arguments, results and device-side errors,
  * but every surviving K/V row is read from HBM once: it is used for the attention of
- * its segment while it is moved.  Two kernels serve it: a one-shot one for up to 5 query
- * heads per KV head (4 at head_dim 64), a loop-shaped one whose cost does not depend on the
- * group for 5 ... 8.  The library runs the two stages one after the other instead - same
- * results - where fusing would not pay: a destination of less than a quarter of the
- * source's capacity (few rows can survive), or a source of more than 67 M entries. */
+ * its segment while it is moved (q.k on the vector ALU, p.v on the matrix cores with the
+ * probabilities split into two bf16 terms: the product is exact to 2^-16 of every term, sums
+ * are fp32; the cost does not depend on the number of query heads per KV head).  With a
+ * destination of less than a quarter of the source's capacity (few rows can survive) the kernel
+ * works a block per chunk of the destination, gathering its rows, instead of a block per chunk
+ * of the source.  The library runs the two stages one after the other instead - same results -
+ * for a source of more than 67 M entries. */
 kvtrim_status kvtrim_compact_attn(kvtrim_ctx *ctx, const kvtrim_cache *src, const uint8_t *keep,
                                   const int32_t *kept, kvtrim_cache *dst, int32_t reserve, const void *q,
                                   int32_t layer_begin, int32_t layer_end, float softmax_scale, float *out,

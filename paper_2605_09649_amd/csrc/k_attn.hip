@@ -265,300 +265,6 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
     }
 }
 
-// Stages 3 + 4 in one pass for groups of query heads too large for the one-shot fused kernel (its G x 8
-// output accumulators per lane have to fit next to a whole batch of rows): the split-K kernel above, reading
-// the SOURCE cache through the list of survivors of its 256-entry run and writing every row it has loaded to
-// the destination as well.  A run is two compaction chunks of one segment (ws.att_desc built over the source
-// with 256-entry chunks lines up with the 128-entry compaction table), so its survivors are contiguous in the
-// destination, from ws.cmp_chunk_dst of its first chunk on.  K travels in MFMA operand layout (loads and
-// stores of 16-byte pieces, lane = row), V and the metadata row by row; plain stores (non-temporal ones and a
-// second, row-wise load of K for coalesced stores both measured slower: 464 / 456 against 442 us).  Layers
-// outside [layer_begin, layer_end) are moved but not attended.
-constexpr int FUSE_RUN = 2 * CMP_CHUNK;      // source entries per block (a multiple of 256; 256 measured best: 426 us
-                                             // against 442 / 461 us for 512 / 1024 at 2.1 M entries and G = 8)
-
-// INPLACE: source and destination are the same cache and every segment keeps its start (tables from
-// launch_cmp_scan_inplace).  A survivor moves left by the number of entries evicted before it, or not at all; the
-// block takes its tiles of 64 survivors in order and, where something moves, lets all four wavefronts finish
-// loading a tile before any of them writes it: a tile's destinations lie at or before its own rows and behind every
-// earlier tile's, never on a later tile's rows.  Survivors whose place lies before the run's own range - where
-// another block may still be reading - go to the same index of `stage`; k_cmp_unstage puts them in place after
-// this kernel has ended.  Rows that stay are not written, and a run that loses nothing and does not move skips
-// the mask and the survivor list altogether.
-template <int D, int G, bool INPLACE>
-__global__ __launch_bounds__(ATT_THREADS) void k_att_fused(CacheView src, const uint8_t* __restrict__ keep,
-                                                           CacheViewMut dst, CacheViewMut stage,
-                                                           const uint16_t* __restrict__ q, Shape sh,
-                                                           Workspace ws, float scale_log2, int layer_begin,
-                                                           int layer_end) {
-    typedef Frag<D> F;
-    typedef typename F::vec vec;
-    constexpr int E = F::E;
-    constexpr int NSTREAM = ATT_THREADS / 64;
-    constexpr int VPR = D / E;                                    // vectors per row = 16
-    __shared__ float s_m[NSTREAM][G], s_l[NSTREAM][G];
-    __shared__ float s_o[NSTREAM][G][D];
-    constexpr int RUN = INPLACE ? FUSE_RUN_INPLACE : FUSE_RUN;    // source entries per block
-    __shared__ int s_list[RUN];
-    __shared__ int s_wcnt[RUN / 64];
-
-    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
-    const int ch = blockIdx.x;
-    // the run and where its survivors go (both tables come from the compaction scan and cover the whole grid; what
-    // they hold at or beyond the run count is not used), fetched together with the two grid-wide words
-    const ChunkDesc cd = ws.att_desc[ch];
-    const int64_t dflag = ws.run_dst[ch];
-    if (__hip_atomic_load(ws.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
-    if (ch >= ws.att_chunk_prefix[sh.nseg]) return;
-    const int seg = cd.seg;
-    const int64_t sbase = cd.first;                               // first source entry of the run
-    const int64_t dbase = dflag & ~CMP_DST_FULL;                  // first destination entry of its survivors
-    // INPLACE: the run loses nothing (all of its chunks are full) ...
-    const bool ident = INPLACE && (dflag & CMP_DST_FULL) != 0;
-    const bool moves = !INPLACE || !(ident && dbase == sbase);    // ... and stays where it is; uniform over the block
-
-    // survivors of the run, in order: passes of 256 entries, ranks from ballots and wavefront counts
-    constexpr int NPASS = RUN / ATT_THREADS;
-    int cnt = 0;
-    float md_lb[NPASS], md_lt[NPASS];                             // INPLACE: the metadata of the thread's entries
-    int md_pos[NPASS], md_rank[NPASS];
-    bool md_mine[NPASS];
-#pragma unroll
-    for (int h = 0; h < NPASS; ++h) {
-        md_lb[h] = md_lt[h] = 0.f;
-        md_pos[h] = 0;
-        md_rank[h] = h * ATT_THREADS + tid;
-        md_mine[h] = false;
-    }
-    if (ident) {
-        cnt = cd.n;
-#pragma unroll
-        for (int h = 0; h < NPASS; ++h) md_mine[h] = moves && h * ATT_THREADS + tid < cd.n;
-    } else {
-        bool flag[NPASS];
-        int rank[NPASS];
-#pragma unroll
-        for (int h = 0; h < NPASS; ++h) {
-            const int i = h * ATT_THREADS + tid;
-            flag[h] = i < cd.n && keep[sbase + i] != 0;
-            const uint64_t mask = __ballot(flag[h]);
-            rank[h] = mbcnt(mask);
-            if (lane == 0) s_wcnt[h * NSTREAM + wave] = __popcll(mask);
-        }
-        __syncthreads();
-#pragma unroll
-        for (int w = 0; w < RUN / 64; ++w) {
-            const int c = s_wcnt[w];
-#pragma unroll
-            for (int h = 0; h < NPASS; ++h)
-                if (w < h * NSTREAM + wave) rank[h] += c;
-            cnt += c;
-        }
-#pragma unroll
-        for (int h = 0; h < NPASS; ++h) {
-            if (flag[h]) {
-                const int i = h * ATT_THREADS + tid;
-                s_list[rank[h]] = i;
-                if (INPLACE) {
-                    md_mine[h] = true;
-                    md_rank[h] = rank[h];
-                } else {
-                    dst.log_beta[dbase + rank[h]] = src.log_beta[sbase + i];
-                    if (src.log_tail) dst.log_tail[dbase + rank[h]] = src.log_tail[sbase + i];
-                    dst.pos[dbase + rank[h]] = src.pos[sbase + i];
-                }
-            }
-        }
-    }
-    if (INPLACE) {
-        // the metadata of every entry of the run is in registers before any of it is overwritten
-#pragma unroll
-        for (int h = 0; h < NPASS; ++h) {
-            const int i = h * ATT_THREADS + tid;
-            if (md_mine[h]) {
-                md_lb[h] = src.log_beta[sbase + i];
-                if (src.log_tail) md_lt[h] = src.log_tail[sbase + i];
-                md_pos[h] = src.pos[sbase + i];
-            }
-        }
-        if (moves) {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
-#pragma unroll
-            for (int h = 0; h < NPASS; ++h) {
-                const int64_t de = dbase + md_rank[h];
-                if (md_mine[h] && de != sbase + h * ATT_THREADS + tid) {
-                    const CacheViewMut& t = de >= sbase ? dst : stage;
-                    t.log_beta[de] = md_lb[h];
-                    if (src.log_tail) t.log_tail[de] = md_lt[h];
-                    t.pos[de] = md_pos[h];
-                }
-            }
-        }
-    } else {
-        __syncthreads();
-    }
-
-    const int c16 = lane & 15, b4 = lane >> 4;
-    const int seq = seg / sh.segs_per_seq, lh = seg % sh.segs_per_seq;
-    const int layer = lh / sh.n_kv_heads, head = lh % sh.n_kv_heads;
-    const bool attend = layer >= layer_begin && layer < layer_end;   // uniform over the block
-    const int64_t qrow = ((int64_t)seq * sh.n_layers + layer) * sh.n_q_heads + (int64_t)head * G + c16;
-    vec qf[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-        qf[j] = attend && c16 < G ? reinterpret_cast<const vec*>(q + qrow * D)[4 * j + b4] : F::zero();
-
-    float o[G][E];
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int e = 0; e < E; ++e) o[g][e] = 0.f;
-    float m = -INFINITY, l = 0.f;
-
-    const vec* kp = reinterpret_cast<const vec*>(src.k);
-    const vec* vp = reinterpret_cast<const vec*>(src.v);
-    const int last = cnt - 1;
-    auto entry_of = [&](int r) { return ident ? r : s_list[r]; };  // entry of the run that survivor r is
-
-    // the three steps of a wavefront's tile of 16 survivors [r0, r0 + 16)
-    auto load_tile = [&](int r0, vec (&kf)[4], vec (&vf)[4], int& ksrc_e, int (&vsrc_e)[4]) {
-        // K in MFMA operand layout: lane -> survivor r0 + c16, vectors 4j + b4
-        ksrc_e = entry_of(min(r0 + c16, last));
-#pragma unroll
-        for (int j = 0; j < 4; ++j) kf[j] = kp[(sbase + ksrc_e) * VPR + 4 * j + b4];
-        // V row by row: lane -> survivor r0 + 4*b4 + i, vector c16
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            vsrc_e[i] = entry_of(min(r0 + 4 * b4 + i, last));
-            vf[i] = vp[(sbase + vsrc_e[i]) * VPR + c16];
-        }
-    };
-    auto store_tile = [&](int r0, const vec (&kf)[4], const vec (&vf)[4], int ksrc_e, const int (&vsrc_e)[4]) {
-        const int kr = r0 + c16;
-        if (kr < cnt && (!INPLACE || dbase + kr != sbase + ksrc_e)) {   // INPLACE: a row that stays is not written
-            vec* kd = reinterpret_cast<vec*>((!INPLACE || dbase + kr >= sbase) ? dst.k : stage.k);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) kd[(dbase + kr) * VPR + 4 * j + b4] = kf[j];
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int row = r0 + 4 * b4 + i;
-            if (row < cnt && (!INPLACE || dbase + row != sbase + vsrc_e[i])) {
-                vec* vd = reinterpret_cast<vec*>((!INPLACE || dbase + row >= sbase) ? dst.v : stage.v);
-                vd[(dbase + row) * VPR + c16] = vf[i];
-            }
-        }
-    };
-    auto attend_tile = [&](int r0, const vec (&kf)[4], const vec (&vf)[4]) {
-        float4v acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc = F::mma(kf[j], qf[j], acc);
-        // acc[i] = q(c16) . k(survivor r0 + 4*b4 + i)
-        float z[4];
-        float tmax = -INFINITY;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            z[i] = r0 + 4 * b4 + i < cnt ? acc[i] * scale_log2 : -INFINITY;
-            tmax = fmaxf(tmax, z[i]);
-        }
-        const float m_new = fmaxf(m, tmax);
-        const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m - m_safe);   // m = -inf gives 0; l and o are 0 then
-        float p[4];
-        float psum = 0.f;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            p[i] = __builtin_amdgcn_exp2f(z[i] - m_safe);
-            psum += p[i];
-        }
-        l = l * alpha + psum;
-        m = m_new;
-        if (__any(alpha != 1.0f)) PV<G, E, 0>::scale(o, alpha);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            float vfl[E];
-            F::unpack(vf[i], vfl);
-            PV<G, E, 0>::run(o, p[i], vfl);
-        }
-    };
-
-    if (!INPLACE) {
-        for (int r0 = wave * 16; r0 < cnt; r0 += 64) {
-            vec kf[4], vf[4];
-            int ke, ve[4];
-            load_tile(r0, kf, vf, ke, ve);
-            store_tile(r0, kf, vf, ke, ve);
-            if (attend) attend_tile(r0, kf, vf);
-        }
-    } else {
-        for (int t0 = 0; t0 < cnt; t0 += 64) {                    // the same trip count in every wavefront
-            const int r0 = t0 + wave * 16;
-            const bool active = r0 < cnt;
-            vec kf[4], vf[4];
-            int ke = 0, ve[4] = {0, 0, 0, 0};
-            if (active) load_tile(r0, kf, vf, ke, ve);
-            if (moves) {
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                __syncthreads();
-                if (active) store_tile(r0, kf, vf, ke, ve);
-            }
-            if (active && attend) attend_tile(r0, kf, vf);
-        }
-    }
-    if (!attend) return;
-
-    // merge as in k_att_partial: the four row-group streams of a wavefront, then the wavefronts through LDS
-    float m_all = fmaxf(m, __shfl_xor(m, 16, 64));
-    m_all = fmaxf(m_all, __shfl_xor(m_all, 32, 64));
-    const float m_fin = m_all == -INFINITY ? 0.f : m_all;
-    const float wgt = __builtin_amdgcn_exp2f(m - m_fin);          // 0 for a stream that saw no row
-    float l_all = l * wgt;
-    l_all += __shfl_xor(l_all, 16, 64);
-    l_all += __shfl_xor(l_all, 32, 64);
-    PV<G, E, 0>::scale(o, wgt);
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int e = 0; e < E; ++e) {
-            float x = o[g][e];
-            x += __shfl_xor(x, 16, 64);
-            x += __shfl_xor(x, 32, 64);
-            o[g][e] = x;
-        }
-    if (b4 == 0) {
-        if (c16 < G) {
-            s_m[wave][c16] = m_all;
-            s_l[wave][c16] = l_all;
-        }
-#pragma unroll
-        for (int g = 0; g < G; ++g)
-#pragma unroll
-            for (int e = 0; e < E; ++e) s_o[wave][g][c16 * E + e] = o[g][e];
-    }
-    __syncthreads();
-    float* part = ws.att_partial + (size_t)ch * G * (D + 2);
-    for (int idx = tid; idx < G * D; idx += ATT_THREADS) {
-        const int g = idx / D, d = idx % D;
-        float M = -INFINITY;
-#pragma unroll
-        for (int s = 0; s < NSTREAM; ++s) M = fmaxf(M, s_m[s][g]);
-        const float Ms = M == -INFINITY ? 0.f : M;
-        float accd = 0.f, lsum = 0.f;
-#pragma unroll
-        for (int s = 0; s < NSTREAM; ++s) {
-            const float w = __builtin_amdgcn_exp2f(s_m[s][g] - Ms);
-            accd += s_o[s][g][d] * w;
-            lsum += s_l[s][g] * w;
-        }
-        part[g * (D + 2) + 2 + d] = accd;
-        if (d == 0) {
-            part[g * (D + 2)] = M;
-            part[g * (D + 2) + 1] = lsum;
-        }
-    }
-}
-
 // One block per segment of the layer range: merges the partial results of its chunks, a tile
 // of COMB_TILE chunks at a time.  Phase A brings the tile's (m, l) pairs into LDS and turns
 // them into weights 2^(m - M); phase B lets every thread sum "its" (query head, d) column over
@@ -699,66 +405,6 @@ kvtrim_status launch_attn(kvtrim_ctx* ctx, const CacheView& c, const uint16_t* q
     }
     if (!ok) return KVTRIM_EINVAL;
     return launch_combine(ctx, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, st);
-}
-
-// The loop-shaped fused pass for G > 4 (k_att_fused): the compaction tables and the run table must be in the
-// workspace (launch_cmp_scan_aligned with run = FUSE_RUN); moves every segment, attends the layer range.
-// Returns false when the group size has no instance.
-bool launch_attn_fused(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const CacheViewMut& dst,
-                       const uint16_t* q, int32_t layer_begin, int32_t layer_end, float scale, hipStream_t st) {
-    const Shape& sh = ctx->shape;
-    const Workspace& ws = ctx->ws;
-    const int64_t max_chunks = src.cap / FUSE_RUN + sh.nseg;      // the run table comes from the compaction scan
-    const float scale_log2 = scale * 1.4426950408889634f;
-    ProfScope prof(ctx, K_ATT_FUSED, st);
-    const dim3 grid((unsigned)max_chunks), block(ATT_THREADS);
-#define KVTRIM_CASE(d, g) \
-    hipLaunchKernelGGL((k_att_fused<d, g, false>), grid, block, 0, st, src, keep, dst, dst, q, sh, ws, scale_log2, layer_begin, layer_end); return true
-    if (sh.head_dim == 128) {
-        switch (sh.group) {
-            case 5: KVTRIM_CASE(128, 5);
-            case 6: KVTRIM_CASE(128, 6);
-            case 7: KVTRIM_CASE(128, 7);
-            case 8: KVTRIM_CASE(128, 8);
-            default: return false;
-        }
-    }
-    switch (sh.group) {
-        case 5: KVTRIM_CASE(64, 5);
-        case 6: KVTRIM_CASE(64, 6);
-        case 7: KVTRIM_CASE(64, 7);
-        case 8: KVTRIM_CASE(64, 8);
-        default: return false;
-    }
-#undef KVTRIM_CASE
-}
-
-// The loop-shaped pass inside the cache (k_att_fused<.., INPLACE>): the in-place compaction tables must be in the
-// workspace (launch_cmp_scan_inplace).  Returns false when the group size has no instance.
-bool launch_attn_fused_inplace(kvtrim_ctx* ctx, const CacheViewMut& c, const uint8_t* keep, const CacheViewMut& stage,
-                               const uint16_t* q, int32_t layer_begin, int32_t layer_end, float scale, hipStream_t st) {
-    const Shape& sh = ctx->shape;
-    const Workspace& ws = ctx->ws;
-    const int64_t max_chunks = c.cap / FUSE_RUN_INPLACE + sh.nseg;
-    const float scale_log2 = scale * 1.4426950408889634f;
-    CacheView src;
-    src.k = c.k; src.v = c.v; src.log_beta = c.log_beta; src.pos = c.pos;
-    src.seg_start = c.seg_start; src.seg_len = c.seg_len; src.cap = c.cap; src.log_tail = c.log_tail;
-    ProfScope prof(ctx, K_ATT_FUSED, st);                         // (the run table comes from the compaction scan)
-    const dim3 grid((unsigned)max_chunks), block(ATT_THREADS);
-#define KVTRIM_CASE(d, g) \
-    case g: hipLaunchKernelGGL((k_att_fused<d, g, true>), grid, block, 0, st, src, keep, c, stage, q, sh, ws, scale_log2, layer_begin, layer_end); return true;
-    if (sh.head_dim == 128) {
-        switch (sh.group) {                                       // (smaller groups: the one-shot kernel's in-place instance)
-            KVTRIM_CASE(128, 7) KVTRIM_CASE(128, 8)
-            default: return false;
-        }
-    }
-    switch (sh.group) {
-        KVTRIM_CASE(64, 7) KVTRIM_CASE(64, 8)
-        default: return false;
-    }
-#undef KVTRIM_CASE
 }
 
 // Attention over the page runs listed in ws.att_desc / ws.att_chunk_prefix (built by the paged plan

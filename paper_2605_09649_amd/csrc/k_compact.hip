@@ -42,7 +42,7 @@ __device__ __forceinline__ void block_sum_n(int64_t (&v)[N], int64_t* lds /* [16
 // they are and there is no capacity to check.
 __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_prefix(CacheView src, const int32_t* __restrict__ kept,
                                                              CacheViewMut dst, int reserve, int align, Shape sh,
-                                                             Workspace ws, int inplace, int run, int gat) {
+                                                             Workspace ws, int inplace, int gat) {
     __shared__ int64_t lds64[17];
     __shared__ int s_bad_layout, s_bad_kept;
     const int tid = threadIdx.x, nseg = sh.nseg;
@@ -61,7 +61,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_prefix(CacheView src, cons
             if (kp < 0 || kp > len) s_bad_kept = 1;
             nch = len > 0 ? ((int64_t)len + CMP_CHUNK - 1) / CMP_CHUNK : 0;
             need = ((int64_t)kp + reserve + align - 1) / align * align;
-            nrun = run > 0 && len > 0 ? ((int64_t)(gat ? kp : len) + run - 1) / run : 0;
+            nrun = gat && len > 0 ? ((int64_t)kp + CMP_CHUNK - 1) / CMP_CHUNK : 0;
         }
         int64_t tot_c, tot_e;
         const int64_t ex_c = block_excl_scan<int64_t>(nch, lds64, &tot_c);
@@ -73,7 +73,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_prefix(CacheView src, cons
         }
         chunks += tot_c;
         entries += tot_e;
-        if (run > 0) {                                            // uniform over the block
+        if (gat) {                                                // uniform over the block
             int64_t tot_r;
             const int64_t ex_r = block_excl_scan<int64_t>(nrun, lds64, &tot_r);
             if (i < nseg) ws.att_chunk_prefix[i] = (int32_t)min(runs + ex_r, (int64_t)0x7fffffff);
@@ -86,10 +86,10 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_prefix(CacheView src, cons
         if (bad_layout || bad_kept || (!inplace && entries > dst.cap)) {
             atomicOr(ws.err, bad_layout ? ERR_LAYOUT : (bad_kept ? ERR_MISMATCH : ERR_CAP));
             ws.cmp_chunk_prefix[nseg] = 0;
-            if (run > 0) ws.att_chunk_prefix[nseg] = 0;
+            if (gat) ws.att_chunk_prefix[nseg] = 0;
         } else {
             ws.cmp_chunk_prefix[nseg] = (int32_t)chunks;
-            if (run > 0) ws.att_chunk_prefix[nseg] = (int32_t)runs;
+            if (gat) ws.att_chunk_prefix[nseg] = (int32_t)runs;
         }
     }
     if (!inplace && !(bad_layout || bad_kept || entries > dst.cap)) {
@@ -99,13 +99,13 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_prefix(CacheView src, cons
 }
 
 // PRE: k_cmp_prefix has run (segment prefixes and the checks over all segments are done).
-// run > 0: the table of `run`-entry runs of all segments (ws.att_chunk_prefix / ws.att_desc, what k_att_plan builds
-// for the whole layer range) is written as well, for the loop-shaped fused kernel that follows.
+// gat: the table of the DESTINATION's 128-row chunks (ws.att_chunk_prefix / ws.att_desc) and the source row of every
+// destination row (ws.gat_src) are written as well, for the gathering instance of the fused kernel that follows.
 template <bool PRE>
 __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const uint8_t* __restrict__ keep,
                                                            const int32_t* __restrict__ kept, CacheViewMut dst,
                                                            int reserve, int align, Shape sh, Workspace ws, int inplace,
-                                                           int run, int gat) {
+                                                           int gat) {
     __shared__ int64_t lds64[17];
     __shared__ int64_t lds_n[16 * 8];
     __shared__ int s_cnt[SCAN_THREADS];
@@ -137,7 +137,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const 
         if (s_err != 0) return;
         chunks_before = ws.cmp_chunk_prefix[g];
         dst_before = dst.seg_start[g];
-        if (run > 0) runs_before = ws.att_chunk_prefix[g];
+        if (gat) runs_before = ws.att_chunk_prefix[g];
     } else if (tid < nseg) {                                      // (nseg <= SCAN_THREADS without k_cmp_prefix)
         o_len = src.seg_len[tid];
         o_st = src.seg_start[tid];
@@ -180,7 +180,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const 
             acc[5] |= (o_kp < 0 || o_kp > o_len);
             const int64_t nc = o_len > 0 ? ((int64_t)o_len + CMP_CHUNK - 1) / CMP_CHUNK : 0;
             const int64_t need = ((int64_t)o_kp + reserve + align - 1) / align * align;   // align = 1 unless pages are built
-            const int64_t nrun = run > 0 && o_len > 0 ? ((int64_t)(gat ? o_kp : o_len) + run - 1) / run : 0;
+            const int64_t nrun = gat && o_len > 0 ? ((int64_t)o_kp + CMP_CHUNK - 1) / CMP_CHUNK : 0;
             acc[3] += nc;
             acc[2] += need;
             acc[7] += nrun;
@@ -202,7 +202,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const 
                 atomicOr(ws.err, bad_layout ? ERR_LAYOUT : (bad_kept ? ERR_MISMATCH : ERR_CAP));
                 if (g == 0) {
                     ws.cmp_chunk_prefix[nseg] = 0;
-                    if (run > 0) ws.att_chunk_prefix[nseg] = 0;
+                    if (gat) ws.att_chunk_prefix[nseg] = 0;
                 }
             }
             return;
@@ -211,16 +211,14 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const 
 
     const int cbase = (int)chunks_before;
     int64_t gat_slots = 0;                                        // gat: slots of this segment in ws.gat_src
-    if (run > 0) {                                                // the segment's runs, for the loop-shaped fused kernel
-        // (gat: the runs are chunks of the DESTINATION segment, for the gathering fused kernel)
-        const int rlen = gat ? (own_ok ? kept[g] : 0) : len;
-        const int64_t rstart = gat ? dst_before : start;
-        const int nrun = len > 0 && rlen > 0 ? (int)(((int64_t)rlen + run - 1) / run) : 0;
-        if (gat) gat_slots = (int64_t)nrun * CMP_CHUNK;
+    if (gat) {                                                    // the chunks of the DESTINATION segment, for the gathering fused kernel
+        const int rlen = own_ok ? kept[g] : 0;
+        const int nrun = len > 0 && rlen > 0 ? (rlen + CMP_CHUNK - 1) / CMP_CHUNK : 0;
+        gat_slots = (int64_t)nrun * CMP_CHUNK;
         for (int u = tid; u < nrun; u += SCAN_THREADS) {
             ChunkDesc d;
-            d.first = rstart + (int64_t)u * run;
-            d.n = min(run, rlen - u * run);
+            d.first = dst_before + (int64_t)u * CMP_CHUNK;
+            d.n = min(CMP_CHUNK, rlen - u * CMP_CHUNK);
             d.seg = g;
             ws.att_desc[runs_before + u] = d;
         }
@@ -282,19 +280,6 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_cmp_scan(CacheView src, const 
     if (gat) {
         // the slots behind the segment's last row, up to the end of its last chunk, name a row that exists
         for (int64_t r = running + tid; r < gat_slots; r += SCAN_THREADS) ws.gat_src[runs_before * CMP_CHUNK + r] = (int32_t)start;
-    } else if (run > 0) {
-        // per run: where its survivors go, and whether every one of its chunks is full (the chunk entries above
-        // were written by other threads of this block)
-        __syncthreads();
-        const int rc = run / CMP_CHUNK;
-        const int nrun = (nch + rc - 1) / rc;
-        for (int u = tid; u < nrun; u += SCAN_THREADS) {
-            const int c0 = cbase + u * rc;
-            int64_t v0 = ws.cmp_chunk_dst[c0];
-            bool all_full = (v0 & CMP_DST_FULL) != 0;
-            for (int c = 1; c < rc && u * rc + c < nch; ++c) all_full = all_full && (ws.cmp_chunk_dst[c0 + c] & CMP_DST_FULL) != 0;
-            ws.run_dst[runs_before + u] = (v0 & ~CMP_DST_FULL) | (all_full ? CMP_DST_FULL : 0);
-        }
     }
     if (tid == 0) {
         if (running != kept[g]) atomicOr(ws.err, ERR_MISMATCH);
@@ -476,41 +461,39 @@ __global__ __launch_bounds__(GAT_WAVES * 64) void k_cmp_gather(CacheView src, co
 }
 
 void launch_cmp_scan_aligned(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const int32_t* kept,
-                             const CacheViewMut& dst, int32_t reserve, int32_t align, int32_t run, hipStream_t st,
-                             bool gat) {
+                             const CacheViewMut& dst, int32_t reserve, int32_t align, hipStream_t st, bool gat) {
     ProfScope prof(ctx, K_CMP_SCAN, st);
     const int g = gat ? 1 : 0;
     if (ctx->shape.nseg > 1024) {                                 // see k_cmp_prefix
-        hipLaunchKernelGGL(k_cmp_prefix, dim3(1), dim3(SCAN_THREADS), 0, st, src, kept, dst, reserve, align, ctx->shape, ctx->ws, 0, run, g);
+        hipLaunchKernelGGL(k_cmp_prefix, dim3(1), dim3(SCAN_THREADS), 0, st, src, kept, dst, reserve, align, ctx->shape, ctx->ws, 0, g);
         hipLaunchKernelGGL(k_cmp_scan<true>, dim3(ctx->shape.nseg), dim3(SCAN_THREADS), 0, st, src, keep, kept, dst, reserve,
-                           align, ctx->shape, ctx->ws, 0, run, g);
+                           align, ctx->shape, ctx->ws, 0, g);
     } else {
         hipLaunchKernelGGL(k_cmp_scan<false>, dim3(ctx->shape.nseg), dim3(SCAN_THREADS), 0, st, src, keep, kept, dst, reserve,
-                           align, ctx->shape, ctx->ws, 0, run, g);
+                           align, ctx->shape, ctx->ws, 0, g);
     }
 }
 
 // The tables for a compaction inside the cache itself: every segment keeps its start, chunk ch's survivors go to
 // ws.cmp_chunk_dst[ch] = seg_start + survivors of the segment's earlier chunks; nothing of the cache is written.
-void launch_cmp_scan_inplace(kvtrim_ctx* ctx, const CacheViewMut& c, const uint8_t* keep, const int32_t* kept, int32_t run,
-                             hipStream_t st) {
+void launch_cmp_scan_inplace(kvtrim_ctx* ctx, const CacheViewMut& c, const uint8_t* keep, const int32_t* kept, hipStream_t st) {
     ProfScope prof(ctx, K_CMP_SCAN, st);
     CacheView src;
     src.k = c.k; src.v = c.v; src.log_beta = c.log_beta; src.pos = c.pos;
     src.seg_start = c.seg_start; src.seg_len = c.seg_len; src.cap = c.cap; src.log_tail = c.log_tail;
     if (ctx->shape.nseg > 1024) {
-        hipLaunchKernelGGL(k_cmp_prefix, dim3(1), dim3(SCAN_THREADS), 0, st, src, kept, c, 0, 1, ctx->shape, ctx->ws, 1, run, 0);
+        hipLaunchKernelGGL(k_cmp_prefix, dim3(1), dim3(SCAN_THREADS), 0, st, src, kept, c, 0, 1, ctx->shape, ctx->ws, 1, 0);
         hipLaunchKernelGGL(k_cmp_scan<true>, dim3(ctx->shape.nseg), dim3(SCAN_THREADS), 0, st, src, keep, kept, c, 0, 1,
-                           ctx->shape, ctx->ws, 1, run, 0);
+                           ctx->shape, ctx->ws, 1, 0);
     } else {
         hipLaunchKernelGGL(k_cmp_scan<false>, dim3(ctx->shape.nseg), dim3(SCAN_THREADS), 0, st, src, keep, kept, c, 0, 1,
-                           ctx->shape, ctx->ws, 1, run, 0);
+                           ctx->shape, ctx->ws, 1, 0);
     }
 }
 
 void launch_cmp_scan(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const int32_t* kept,
                      const CacheViewMut& dst, int32_t reserve, hipStream_t st) {
-    launch_cmp_scan_aligned(ctx, src, keep, kept, dst, reserve, 1, 0, st);
+    launch_cmp_scan_aligned(ctx, src, keep, kept, dst, reserve, 1, st);
 }
 
 kvtrim_status launch_compact(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const int32_t* kept,

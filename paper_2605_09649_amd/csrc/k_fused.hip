@@ -31,6 +31,8 @@ constexpr int FUS_THREADS = CMP_THREADS;
 typedef unsigned v4u __attribute__((ext_vector_type(4)));
 typedef unsigned v2u __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float float4v __attribute__((ext_vector_type(4)));
 
 // acc + a.lo * b.lo + a.hi * b.hi on a pair of packed bf16 values (products and sum in fp32)
 __device__ __forceinline__ float dot2_bf16(unsigned a, unsigned b, float acc) {
@@ -125,7 +127,8 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
     __shared__ int wave_cnt[CMP_CHUNK / 64];
     __shared__ int list[CMP_CHUNK];
     __shared__ float s_m[NW][G], s_l[NW][G];
-    __shared__ float s_o[NW][G][D];
+    constexpr int SO = D + 8;                                     // floats per (wavefront, head) in s_o: a 32-byte skew between heads
+    __shared__ __attribute__((aligned(16))) float s_o[NW][G][SO];
 
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int ch = blockIdx.x;
@@ -283,58 +286,73 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
             t.pos[de] = md_pos;
         }
     };
-    // Attention of this wavefront's 16 rows, one query head at a time from q.k to the partial result: each 16-lane row
-    // group takes a softmax partial over its 4 rows, the four row groups are merged with lane shuffles, and the
-    // wavefront's partial for the head goes to LDS at once, so that the accumulators of one head are alive at a time,
-    // not those of all G (74 instead of 84-115 registers at G = 4, head_dim 128: three blocks per compute unit
-    // instead of two; the in-place instance went from 277 to 239 us at the long-context workload).
+    // Attention of this wavefront's 16 rows.
+    //   q.k   on the vector ALU, packed: 4 (2) two-element bf16 dot products per query head, row and lane, then a
+    //         16-lane all-reduce with DPP - every lane ends up with the logits of its 4 rows for every head.
+    //   p.v   on the matrix cores.  A lane holds the same 8 (4) columns of 4 rows, i.e. for one column 4 values along
+    //         the reduction (row) dimension - the operand layout of a 16x16x32 MFMA with m = the lane's column block
+    //         (lane & 15), k = 8 (lane >> 4) + j: slots j = 0..3 carry the lane's rows u = j, slots 4..7 the same rows
+    //         again.  The other operand carries, for n = head (lane & 15 again: lane (sub, g) serves head g), the
+    //         probabilities of those rows as TWO bf16 values each, rounded value in slots 0..3 and the rounded
+    //         remainder in 4..7, so that the product is exact to 2^-16 of every term (V is bf16 anyway, sums are
+    //         fp32).  One MFMA per column of the lane's slice sums over all 16 rows of the wavefront and all G heads
+    //         at once; its result - lane (sub, g): columns 8 (4 sub + i) + e, i = 0..3, of head g - goes to LDS.
+    //         (On the vector ALU the same product took 128 instructions per head; the in-place instance, which moves
+    //         few rows, was bound by them from G = 4 on.)
     auto attend_rows = [&](const vec (&kk)[4], const vec (&vv)[4], const vec (&qp)[G]) {
-        bool valid[4];
+        float zs[4];                                              // logits of this lane's head (lane & 15; lanes >= G: head G - 1, unused)
 #pragma unroll
-        for (int u = 0; u < 4; ++u) valid[u] = r0 + u * 4 + sub < cnt;
+        for (int u = 0; u < 4; ++u) {
+            const bool valid = r0 + u * 4 + sub < cnt;
+            float zu = 0.f;
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            float z[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int g = 0; g < G; ++g) {
                 const float s = row16_sum(R::dot(qp[g], kk[u]));
-                z[u] = valid[u] ? s * scale_log2 : -INFINITY;
+                zu = (g == 0 || col >= g) ? s : zu;               // (ends as head min(col, G - 1))
             }
-            const float mx = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
-            float m_all = fmaxf(mx, __shfl_xor(mx, 16, 64));
-            m_all = fmaxf(m_all, __shfl_xor(m_all, 32, 64));      // maximum over the wavefront's 16 rows
-            const float m_fin = m_all == -INFINITY ? 0.f : m_all;
-            float p[4];
+            zs[u] = valid ? zu * scale_log2 : -INFINITY;
+        }
+        const float mx = fmaxf(fmaxf(zs[0], zs[1]), fmaxf(zs[2], zs[3]));
+        float m_all = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        m_all = fmaxf(m_all, __shfl_xor(m_all, 32, 64));          // maximum over the wavefront's 16 rows
+        const float m_fin = m_all == -INFINITY ? 0.f : m_all;
+        float p[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) p[u] = __builtin_amdgcn_exp2f(z[u] - m_fin);
-            float l_all = (p[0] + p[1]) + (p[2] + p[3]);
-            l_all += __shfl_xor(l_all, 16, 64);
-            l_all += __shfl_xor(l_all, 32, 64);
-            float og[E];
+        for (int u = 0; u < 4; ++u) p[u] = __builtin_amdgcn_exp2f(zs[u] - m_fin);
+        float l_all = (p[0] + p[1]) + (p[2] + p[3]);
+        l_all += __shfl_xor(l_all, 16, 64);
+        l_all += __shfl_xor(l_all, 32, 64);
+        if (sub == 0 && col < G) {
+            s_m[wave][col] = m_all;
+            s_l[wave][col] = l_all;
+        }
+        // p = hi + lo + O(2^-16 p), both bf16 (round to nearest even)
+        const bf16x2 h01 = {(__bf16)p[0], (__bf16)p[1]}, h23 = {(__bf16)p[2], (__bf16)p[3]};
+        const bf16x2 l01 = {(__bf16)(p[0] - (float)h01.x), (__bf16)(p[1] - (float)h01.y)};
+        const bf16x2 l23 = {(__bf16)(p[2] - (float)h23.x), (__bf16)(p[3] - (float)h23.y)};
+        const uint4 pb = make_uint4(__builtin_bit_cast(unsigned, h01), __builtin_bit_cast(unsigned, h23),
+                                    __builtin_bit_cast(unsigned, l01), __builtin_bit_cast(unsigned, l23));
+        float4v acc[E];
 #pragma unroll
-            for (int w = 0; w < E / 2; ++w) {                     // V is unpacked a 32-bit word (two columns) at a time
-                float a = 0.f, b = 0.f;
+        for (int w = 0; w < E / 2; ++w) {
+            const unsigned x0 = R::word(vv[0], w), x1 = R::word(vv[1], w), x2 = R::word(vv[2], w), x3 = R::word(vv[3], w);
+            // columns 2 w (low halves) and 2 w + 1 (high halves) of the four rows
+            const unsigned a01 = __builtin_amdgcn_perm(x1, x0, 0x05040100u), a23 = __builtin_amdgcn_perm(x3, x2, 0x05040100u);
+            const unsigned b01 = __builtin_amdgcn_perm(x1, x0, 0x07060302u), b23 = __builtin_amdgcn_perm(x3, x2, 0x07060302u);
+            const float4v zero = {0.f, 0.f, 0.f, 0.f};
+            acc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, make_uint4(a01, a23, a01, a23)),
+                                                                 __builtin_bit_cast(bf16x8, pb), zero, 0, 0, 0);
+            acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, make_uint4(b01, b23, b01, b23)),
+                                                                     __builtin_bit_cast(bf16x8, pb), zero, 0, 0, 0);
+        }
+        if (col < G) {
+            // s_o[wave][head][(4 i + sub) E + e] = column E (4 sub + i) + e: the four lanes of a head write 4 E contiguous floats
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    unsigned x = R::word(vv[u], w);
-                    asm volatile("" : "+v"(x));                   // (unpacked again for every head: kept unpacked, V costs 2 E registers more)
-                    a = fmaf(p[u], __uint_as_float(x << 16), a);
-                    b = fmaf(p[u], __uint_as_float(x & 0xffff0000u), b);
-                }
-                a += __shfl_xor(a, 16, 64);
-                a += __shfl_xor(a, 32, 64);
-                b += __shfl_xor(b, 16, 64);
-                b += __shfl_xor(b, 32, 64);
-                og[2 * w] = a;
-                og[2 * w + 1] = b;
-            }
-            if (sub == 0) {
+            for (int i = 0; i < 4; ++i) {
+                float* o = &s_o[wave][col][(4 * i + sub) * E];
 #pragma unroll
-                for (int e = 0; e < E; ++e) s_o[wave][g][col * E + e] = og[e];
-            }
-            if (lane == 0) {
-                s_m[wave][g] = m_all;
-                s_l[wave][g] = l_all;
+                for (int e4 = 0; e4 < E; e4 += 4)
+                    *reinterpret_cast<float4*>(o + e4) = make_float4(acc[e4][i], acc[e4 + 1][i], acc[e4 + 2][i], acc[e4 + 3][i]);
             }
         }
     };
@@ -374,6 +392,8 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
     float* part = ws.att_partial + (size_t)ch * G * (D + 2);
     for (int idx = tid; idx < G * D; idx += FUS_THREADS) {
         const int g = idx / D, d = idx % D;
+        const int cb = d / E;                                     // column block 4 sub + i sits at 4 i + sub (see attend_rows)
+        const int so_at = (4 * (cb & 3) + (cb >> 2)) * E + d % E;
         float M = -INFINITY;
 #pragma unroll
         for (int s = 0; s < NW; ++s)
@@ -384,7 +404,7 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
         for (int s = 0; s < NW; ++s) {
             if (s < nw) {
                 const float w = __builtin_amdgcn_exp2f(s_m[s][g] - Ms);
-                accd += s_o[s][g][d] * w;
+                accd += s_o[s][g][so_at] * w;
                 lsum += s_l[s][g] * w;
             }
         }
@@ -403,9 +423,9 @@ static bool dispatch_fused(int G, dim3 grid, hipStream_t st, const CacheView& sr
     switch (G) {
 #define KVTRIM_CASE(g) \
     case g: hipLaunchKernelGGL((k_cmp_attn<D, g, INPLACE>), grid, dim3(FUS_THREADS), 0, st, src, keep, dst, stage, q, sh, ws, scale_log2, lb, le); return true;
-        KVTRIM_CASE(1) KVTRIM_CASE(2) KVTRIM_CASE(3) KVTRIM_CASE(4) KVTRIM_CASE(5) KVTRIM_CASE(6)
+        KVTRIM_CASE(1) KVTRIM_CASE(2) KVTRIM_CASE(3) KVTRIM_CASE(4) KVTRIM_CASE(5) KVTRIM_CASE(6) KVTRIM_CASE(7) KVTRIM_CASE(8)
 #undef KVTRIM_CASE
-        default: return false;                                    // larger groups take the loop-shaped kernel (k_att_fused)
+        default: return false;
     }
 }
 
@@ -415,7 +435,7 @@ static bool dispatch_gather(int G, dim3 grid, hipStream_t st, const CacheView& s
     switch (G) {
 #define KVTRIM_CASE(g) \
     case g: hipLaunchKernelGGL((k_cmp_attn<D, g, false, false, true>), grid, dim3(FUS_THREADS), 0, st, src, nullptr, dst, dst, q, sh, ws, scale_log2, lb, le); return true;
-        KVTRIM_CASE(1) KVTRIM_CASE(2) KVTRIM_CASE(3) KVTRIM_CASE(4) KVTRIM_CASE(5)
+        KVTRIM_CASE(1) KVTRIM_CASE(2) KVTRIM_CASE(3) KVTRIM_CASE(4) KVTRIM_CASE(5) KVTRIM_CASE(6) KVTRIM_CASE(7) KVTRIM_CASE(8)
 #undef KVTRIM_CASE
         default: return false;
     }
@@ -428,12 +448,9 @@ static bool dispatch_gather(int G, dim3 grid, hipStream_t st, const CacheView& s
 // no kernel of the call reads any more.
 constexpr int UNS_THREADS = 256;
 
-// run_chunks: chunks per block of the kernel that parked the rows (1: k_cmp_attn, 2: k_att_fused); a block parks
-// only what belongs before its whole run, so the later chunks of a run have nothing parked.
 template <int D>
 __global__ __launch_bounds__(UNS_THREADS) void k_cmp_unstage(CacheViewMut c, CacheViewMut stage,
-                                                             const int32_t* __restrict__ kept, Shape sh, Workspace ws,
-                                                             int run_chunks) {
+                                                             const int32_t* __restrict__ kept, Shape sh, Workspace ws) {
     constexpr int VPR = D / 8;                                    // 16-byte vectors per row
     const int lane = lane_id();
     const int ch = blockIdx.x * (UNS_THREADS / 64) + (threadIdx.x >> 6);
@@ -445,10 +462,9 @@ __global__ __launch_bounds__(UNS_THREADS) void k_cmp_unstage(CacheViewMut c, Cac
     const int first_ch = ws.cmp_chunk_prefix[seg];
     if (ch == first_ch && lane == 0) c.seg_len[seg] = kept[seg];
     if (cd.first == dbase) return;                                // nothing was evicted before this chunk
-    if ((ch - first_ch) % run_chunks) return;                     // not the first chunk of its run
-    const bool last = ch + run_chunks >= ws.cmp_chunk_prefix[seg + 1];
-    const int64_t dnext = last ? c.seg_start[seg] + kept[seg] : (ws.cmp_chunk_dst[ch + run_chunks] & ~CMP_DST_FULL);
-    const int64_t staged = min(cd.first - dbase, dnext - dbase);  // survivors that belong before the run's own range
+    const bool last = ch + 1 >= ws.cmp_chunk_prefix[seg + 1];
+    const int64_t dnext = last ? c.seg_start[seg] + kept[seg] : (ws.cmp_chunk_dst[ch + 1] & ~CMP_DST_FULL);
+    const int64_t staged = min(cd.first - dbase, dnext - dbase);  // survivors that belong before the chunk's own range
     const uint4* sk = reinterpret_cast<const uint4*>(stage.k) + dbase * VPR;
     const uint4* sv = reinterpret_cast<const uint4*>(stage.v) + dbase * VPR;
     uint4* dk = reinterpret_cast<uint4*>(c.k) + dbase * VPR;
@@ -559,7 +575,7 @@ kvtrim_status launch_compact_inplace(kvtrim_ctx* ctx, const CacheViewMut& c, con
     const Shape& sh = ctx->shape;
     const Workspace& ws = ctx->ws;
     const int64_t max_chunks = c.cap / CMP_CHUNK + sh.nseg;
-    launch_cmp_scan_inplace(ctx, c, keep, kept, 0, st);
+    launch_cmp_scan_inplace(ctx, c, keep, kept, st);
     {
         ProfScope prof(ctx, K_CMP_COPY, st);
         if (sh.head_dim == 128)
@@ -571,17 +587,13 @@ kvtrim_status launch_compact_inplace(kvtrim_ctx* ctx, const CacheViewMut& c, con
         ProfScope prof(ctx, K_CMP_UNSTAGE, st);
         const dim3 grid((unsigned)((max_chunks + UNS_THREADS / 64 - 1) / (UNS_THREADS / 64)));
         if (sh.head_dim == 128)
-            hipLaunchKernelGGL(k_cmp_unstage<128>, grid, dim3(UNS_THREADS), 0, st, c, stage, kept, sh, ws, 1);
+            hipLaunchKernelGGL(k_cmp_unstage<128>, grid, dim3(UNS_THREADS), 0, st, c, stage, kept, sh, ws);
         else
-            hipLaunchKernelGGL(k_cmp_unstage<64>, grid, dim3(UNS_THREADS), 0, st, c, stage, kept, sh, ws, 1);
+            hipLaunchKernelGGL(k_cmp_unstage<64>, grid, dim3(UNS_THREADS), 0, st, c, stage, kept, sh, ws);
     }
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;
 }
-
-// Largest group of query heads the one-shot fused kernel is used for (beyond it, the loop-shaped one).
-constexpr int FUSED_ONE_SHOT_MAX_G_128 = 5, FUSED_ONE_SHOT_MAX_G_64 = 4;
-constexpr int FUSE_RUN_ENTRIES = 2 * CMP_CHUNK;                   // source entries per block of the loop-shaped fused kernel
 
 kvtrim_status launch_compact_attn(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const int32_t* kept,
                                   const CacheViewMut& dst, int32_t reserve, const uint16_t* q, int32_t layer_begin,
@@ -590,32 +602,20 @@ kvtrim_status launch_compact_attn(kvtrim_ctx* ctx, const CacheView& src, const u
     const Shape& sh = ctx->shape;
     const Workspace& ws = ctx->ws;
     const int64_t max_chunks = src.cap / CMP_CHUNK + sh.nseg;
-    // The one-shot fused kernel does q.k and p.v on the vector ALU with G query heads' worth of accumulators per lane:
-    // its time grows with G (2.1 M retained entries, head_dim 128: 363-404 us for G = 1..5, 443 us at G = 6, 804 /
-    // 863 us at G = 7 / 8, where the accumulators no longer fit the register file; head_dim 64: 184-227 us for
-    // G = 1..4, 255 us at G = 5).  The loop-shaped fused kernel (k_att_fused) takes 421-423 us at head_dim 128 and
-    // 242-247 us at head_dim 64 whatever the group, the two calls 553-578 us and 276-285 us.
-    const bool alu_fits = sh.head_dim == 128 ? sh.group <= FUSED_ONE_SHOT_MAX_G_128 : sh.group <= FUSED_ONE_SHOT_MAX_G_64;
+    // (The fused kernel's time does not depend on the group of query heads: 2.1 M retained entries, G = 1..8: 366-378 us
+    // at head_dim 128, 180-199 us at head_dim 64 - p.v runs on the matrix cores for all heads at once.)
     // Few survivors per source chunk?  A caller that names the evictions of the step (kvtrim_decode_step's evict_hint)
     // has said so itself: a positive hint means a decode step, every chunk nearly whole.  Without a hint the
     // capacities decide, in the one direction in which they can: a destination under a quarter of the source cannot
     // take more than one source entry in four.
     const bool sparse = evict_hint > 0 ? false : dst.cap < src.cap / 4;
-    if (!sparse && !alu_fits && sh.group >= 5 && src.cap / FUSE_RUN_ENTRIES + sh.nseg <= ws.max_att_chunks &&
-        max_chunks <= ws.max_cmp_chunks) {
-        // Large groups of query heads: the loop-shaped fused kernel (the split-K attention kernel reading the source
-        // through the survivor lists and writing the rows out as well), whose cost hardly depends on G.
-        launch_cmp_scan_aligned(ctx, src, keep, kept, dst, reserve, 1, FUSE_RUN_ENTRIES, st);
-        if (!launch_attn_fused(ctx, src, keep, dst, q, layer_begin, layer_end, scale, st)) return KVTRIM_EINVAL;
-        return launch_combine(ctx, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, st);
-    }
     const int64_t dst_chunks = dst.cap / CMP_CHUNK + sh.nseg;    // upper bound on the destination's chunks
-    if (sparse && alu_fits && dst_chunks <= ws.max_att_chunks && dst_chunks * CMP_CHUNK <= ws.gat_slots &&
+    if (sparse && dst_chunks <= ws.max_att_chunks && dst_chunks * CMP_CHUNK <= ws.gat_slots &&
         max_chunks <= ws.max_cmp_chunks) {
         // Few survivors per source chunk: the fused kernel's gathering instance, a block per chunk of the destination
         // (a block per source chunk would write one partial result per 128 source entries for a handful of survivors
         // each).  The compaction scan lists the destination's chunks and the source row of each of their rows.
-        launch_cmp_scan_aligned(ctx, src, keep, kept, dst, reserve, 1, CMP_CHUNK, st, true);
+        launch_cmp_scan_aligned(ctx, src, keep, kept, dst, reserve, 1, st, true);
         bool ok;
         {
             ProfScope prof(ctx, K_CMP_ATTN, st);
@@ -627,10 +627,9 @@ kvtrim_status launch_compact_attn(kvtrim_ctx* ctx, const CacheView& src, const u
         if (!ok) return KVTRIM_EINVAL;
         return launch_combine(ctx, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, st);
     }
-    if (max_chunks > ws.max_att_chunks || sparse || !alu_fits) {
+    if (max_chunks > ws.max_att_chunks || sparse) {
         // Run the two stages one after the other, which computes the same thing: when there are too many source
-        // chunks for the partial-result buffer, for groups of query heads the one-shot kernel does not serve, and
-        // for a sparse selection the gathering instance cannot take.
+        // chunks for the partial-result buffer, and for a sparse selection the gathering instance cannot take.
         kvtrim_status rc = launch_compact(ctx, src, keep, kept, dst, reserve, st);
         if (rc != KVTRIM_OK) return rc;
         CacheView d;
@@ -660,14 +659,9 @@ kvtrim_status launch_compact_attn_inplace(kvtrim_ctx* ctx, const CacheViewMut& c
     CacheView src;
     src.k = c.k; src.v = c.v; src.log_beta = c.log_beta; src.pos = c.pos;
     src.seg_start = c.seg_start; src.seg_len = c.seg_len; src.cap = c.cap; src.log_tail = c.log_tail;
-    launch_cmp_scan_inplace(ctx, c, keep, kept, sh.group > 6 ? FUSE_RUN_INPLACE : 0, st);
-    // up to six query heads per KV head: the one-shot kernel (long-context workload, G = 4: 0.368 ms per step against
-    // 0.382 with the loop-shaped one); seven and eight: the loop-shaped kernel, as out of place
-    const bool loop_shaped = sh.group > 6;
+    launch_cmp_scan_inplace(ctx, c, keep, kept, st);
     bool ok;
-    if (loop_shaped) {
-        ok = launch_attn_fused_inplace(ctx, c, keep, stage, q, layer_begin, layer_end, scale, st);
-    } else {
+    {
         ProfScope prof(ctx, K_CMP_ATTN, st);
         const float scale_log2 = scale * 1.4426950408889634f;
         ok = sh.head_dim == 128
@@ -678,13 +672,12 @@ kvtrim_status launch_compact_attn_inplace(kvtrim_ctx* ctx, const CacheViewMut& c
     {
         ProfScope prof(ctx, K_CMP_UNSTAGE, st);
         const dim3 grid((unsigned)((max_chunks + UNS_THREADS / 64 - 1) / (UNS_THREADS / 64)));
-        const int run_chunks = loop_shaped ? FUSE_RUN_INPLACE / CMP_CHUNK : 1;
         if (sh.head_dim == 128)
-            hipLaunchKernelGGL(k_cmp_unstage<128>, grid, dim3(UNS_THREADS), 0, st, c, stage, kept, sh, ws, run_chunks);
+            hipLaunchKernelGGL(k_cmp_unstage<128>, grid, dim3(UNS_THREADS), 0, st, c, stage, kept, sh, ws);
         else
-            hipLaunchKernelGGL(k_cmp_unstage<64>, grid, dim3(UNS_THREADS), 0, st, c, stage, kept, sh, ws, run_chunks);
+            hipLaunchKernelGGL(k_cmp_unstage<64>, grid, dim3(UNS_THREADS), 0, st, c, stage, kept, sh, ws);
     }
-    return launch_combine(ctx, loop_shaped ? ws.att_chunk_prefix : ws.cmp_chunk_prefix, layer_begin, layer_end, out, lse, st);
+    return launch_combine(ctx, ws.cmp_chunk_prefix, layer_begin, layer_end, out, lse, st);
 }
 
 kvtrim_status launch_decode_step(kvtrim_ctx* ctx, const CacheViewMut& srcm, const StepArgs& sa, const int32_t* now,
@@ -697,10 +690,9 @@ kvtrim_status launch_decode_step(kvtrim_ctx* ctx, const CacheViewMut& srcm, cons
     src.k = srcm.k; src.v = srcm.v; src.log_beta = srcm.log_beta; src.pos = srcm.pos;
     src.seg_start = srcm.seg_start; src.seg_len = srcm.seg_len; src.cap = srcm.cap; src.log_tail = srcm.log_tail;
     const int64_t max_chunks = src.cap / CMP_CHUNK + sh.nseg;
-    const bool alu_fits = sh.head_dim == 128 ? sh.group <= FUSED_ONE_SHOT_MAX_G_128 : sh.group <= FUSED_ONE_SHOT_MAX_G_64;
-    // Three kernels (score + resolve, move + attend, merge) when this is a decode step the candidate list can carry
-    // and the one-shot fused kernel serves the shape; otherwise the calls it stands for, one after the other.
-    const bool three = evict_hint > 0 && 8 * (evict_hint + 1) <= (int64_t)ws.fl_cap && alu_fits &&
+    // Three kernels (score + resolve, move + attend, merge) when this is a decode step the candidate list can carry;
+    // otherwise the calls it stands for, one after the other.
+    const bool three = evict_hint > 0 && 8 * (evict_hint + 1) <= (int64_t)ws.fl_cap &&
                        sh.segs_per_seq <= STEP_MAX_SEGS && sh.n_seq <= STEP_MAX_SEQS && sa.n_new <= STEP_MAX_NEW &&
                        max_chunks <= ws.max_att_chunks && max_chunks <= ws.max_cmp_chunks;
     if (!three) {
@@ -720,8 +712,8 @@ kvtrim_status launch_decode_step(kvtrim_ctx* ctx, const CacheViewMut& srcm, cons
         switch (sh.head_dim * 16 + sh.group) {
 #define KVTRIM_CASE(d, g) \
     case d * 16 + g: hipLaunchKernelGGL((k_cmp_attn<d, g, false, true>), grid, block, 0, st, src, (const uint8_t*)sa.keep_out, sa.dst, sa.dst, q, sh, ws, scale_log2, layer_begin, layer_end, srcm.seg_len); break;
-            KVTRIM_CASE(128, 1) KVTRIM_CASE(128, 2) KVTRIM_CASE(128, 3) KVTRIM_CASE(128, 4) KVTRIM_CASE(128, 5)
-            KVTRIM_CASE(64, 1) KVTRIM_CASE(64, 2) KVTRIM_CASE(64, 3) KVTRIM_CASE(64, 4)
+            KVTRIM_CASE(128, 1) KVTRIM_CASE(128, 2) KVTRIM_CASE(128, 3) KVTRIM_CASE(128, 4) KVTRIM_CASE(128, 5) KVTRIM_CASE(128, 6) KVTRIM_CASE(128, 7) KVTRIM_CASE(128, 8)
+            KVTRIM_CASE(64, 1) KVTRIM_CASE(64, 2) KVTRIM_CASE(64, 3) KVTRIM_CASE(64, 4) KVTRIM_CASE(64, 5) KVTRIM_CASE(64, 6) KVTRIM_CASE(64, 7) KVTRIM_CASE(64, 8)
 #undef KVTRIM_CASE
             default: return KVTRIM_EINVAL;
         }

@@ -85,7 +85,6 @@ static Layout layout_of(const kvtrim_config* c, bool select_only) {
     l.off[20] = bump(cur, seg_tables * (size_t)nseg * sizeof(int32_t));        // pg_seg_len
     l.off[21] = bump(cur, (size_t)c->n_seq * sizeof(uint32_t));                // seq_done
     l.off[22] = bump(cur, seg_tables * (size_t)nseg * sizeof(int32_t));        // chunk_old_len
-    l.off[23] = bump(cur, l.max_att_chunks * sizeof(int64_t));                 // run_dst
     // decode-step selection: a candidate list per sequence, shorter when there are many sequences (1 M entries in all)
     int64_t fl = ((int64_t)1 << 20) / c->n_seq / 64 * 64;
     fl = fl > FL_CAP_MAX ? FL_CAP_MAX : (fl < FL_CAP_MIN ? FL_CAP_MIN : fl);
@@ -137,7 +136,6 @@ static void bind(const Layout& l, char* b, Workspace& w) {
     w.pg_seg_len = (int32_t*)(b + l.off[20]);
     w.seq_done = (uint32_t*)(b + l.off[21]);
     w.chunk_old_len = (int32_t*)(b + l.off[22]);
-    w.run_dst = (int64_t*)(b + l.off[23]);
     w.fast_hi = (uint32_t*)(b + l.off[24]);
     w.fast_min = (uint32_t*)(b + l.off[25]);
     w.fast_done = (uint32_t*)(b + l.off[26]);
@@ -298,7 +296,7 @@ static const char* const kernel_names[KVTRIM_N_KERNELS] = {
     "k_score", "k_sel_plan", "k_sel_hist<0>", "k_sel_hist<1>", "k_sel_hist<2>", "k_sel_count", "k_sel_mask",
     "k_cmp_scan", "k_cmp_copy", "k_att_plan", "k_att_partial", "k_att_combine", "k_append", "k_cmp_attn", "k_occupancy",
     "k_pg_init", "k_pg_append", "k_pg_score", "k_pg_plan", "k_pg_count", "k_pg_evict", "k_pg_tidy", "k_pg_att_plan", "k_gate_hidden", "k_gate_readout",
-    "k_gate_fold", "k_gate_prefill", "k_gate_retile", "k_pg_defrag", "k_gate_dot", "k_att_fused", "k_cmp_unstage",
+    "k_gate_fold", "k_gate_prefill", "k_gate_retile", "k_pg_defrag", "k_gate_dot", "reserved30", "k_cmp_unstage",
     "k_fast_scan", "k_fast_mask", "reserved34", "reserved35", "reserved36", "reserved37", "reserved38", "reserved39"};
 
 const char* kvtrim_kernel_name(int32_t id) { return id >= 0 && id < KVTRIM_N_KERNELS ? kernel_names[id] : nullptr; }

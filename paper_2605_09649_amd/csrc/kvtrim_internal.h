@@ -12,8 +12,6 @@ constexpr int SEL_CHUNK = 2048;      // selection: entries per chunk
 constexpr int SEL_SHIFT = 11;        // log2(SEL_CHUNK)
 static_assert((1 << SEL_SHIFT) == SEL_CHUNK, "SEL_SHIFT out of step with SEL_CHUNK");
 constexpr int CMP_CHUNK = 128;       // compaction: entries per block
-constexpr int FUSE_RUN_INPLACE = 256;  // entries per block of the loop-shaped fused kernel's in-place instance (a multiple of
-                                       // 256; runs of 512 measured slower: 0.157 against 0.150 ms per step at G = 7, two sequences)
 constexpr long long CMP_DST_FULL = 1ll << 62;   // flag in ws.cmp_chunk_dst: every entry of the chunk survives
 constexpr int CMP_WAVE_ROWS = 16;    // rows a wavefront moves (one batch of loads, one of stores)
 constexpr int CMP_THREADS = CMP_CHUNK / CMP_WAVE_ROWS * 64;   // 512: one wavefront per 16 survivors
@@ -170,7 +168,6 @@ struct Workspace {
     ChunkDesc* cmp_desc;         // [max_cmp_chunks]
     int64_t* cmp_chunk_dst;      // [max_cmp_chunks] first dst entry of the chunk's survivors (| CMP_DST_FULL)
     int32_t* att_pages;          // [max_att_chunks][4] paged attention: the pages of a chunk, beside its descriptor (| ATT_PAGE_FULL)
-    int64_t* run_dst;            // [max_att_chunks] the same per run of the loop-shaped fused kernel (flag: every chunk of the run is full)
     // attention
     int32_t* att_chunk_prefix;   // [nseg+1]
     ChunkDesc* att_desc;         // [max_att_chunks]
@@ -208,7 +205,7 @@ namespace kvtrim {
 enum KernelId {
     K_SCORE = 0, K_SEL_PLAN, K_SEL_HIST0, K_SEL_HIST1, K_SEL_HIST2, K_SEL_COUNT, K_SEL_MASK,
     K_CMP_SCAN, K_CMP_COPY, K_ATT_PLAN, K_ATT_PARTIAL, K_ATT_COMBINE, K_APPEND, K_CMP_ATTN, K_OCCUPANCY,
-    K_PG_INIT, K_PG_APPEND, K_PG_SCORE, K_PG_PLAN, K_PG_COUNT, K_PG_EVICT, K_PG_TIDY, K_PG_ATT_PLAN, K_GATE_HIDDEN, K_GATE_READOUT, K_GATE_FOLD, K_GATE_PREFILL, K_GATE_RETILE, K_PG_DEFRAG, K_GATE_DOT, K_ATT_FUSED, K_CMP_UNSTAGE,
+    K_PG_INIT, K_PG_APPEND, K_PG_SCORE, K_PG_PLAN, K_PG_COUNT, K_PG_EVICT, K_PG_TIDY, K_PG_ATT_PLAN, K_GATE_HIDDEN, K_GATE_READOUT, K_GATE_FOLD, K_GATE_PREFILL, K_GATE_RETILE, K_PG_DEFRAG, K_GATE_DOT, K_RESERVED_30, K_CMP_UNSTAGE,
     K_FAST_SCAN, K_FAST_MASK, K_RESERVED_34, K_RESERVED_35, K_RESERVED_36, K_RESERVED_37, K_RESERVED_38, K_RESERVED_39, K_COUNT
 };
 static_assert(K_COUNT == KVTRIM_N_KERNELS, "kernel table out of step with the header");
@@ -266,25 +263,18 @@ kvtrim_status launch_attn_paged(kvtrim_ctx*, const CacheView& pool, const int32_
                                 int max_chunks,
                                 int32_t layer_begin, int32_t layer_end, float scale, float* out, float* lse,
                                 hipStream_t);
-// run > 0: also writes the table of `run`-entry runs of all segments that the loop-shaped fused kernel reads
-// (ws.att_chunk_prefix / ws.att_desc), so that no separate plan kernel is needed.
-// gat: the runs are CMP_CHUNK-row chunks of the DESTINATION segments (run = CMP_CHUNK), and ws.gat_src gets the source
-// row of every destination row - what the gathering instance of the fused kernel reads.
+// gat: also writes the table of the DESTINATION's CMP_CHUNK-row chunks (ws.att_chunk_prefix / ws.att_desc) and the source
+// row of every destination row (ws.gat_src) - what the gathering instance of the fused kernel reads.
 void launch_cmp_scan_aligned(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const int32_t* kept,
-                             const CacheViewMut& dst, int32_t reserve, int32_t align, int32_t run, hipStream_t,
-                             bool gat = false);
+                             const CacheViewMut& dst, int32_t reserve, int32_t align, hipStream_t, bool gat = false);
 kvtrim_status launch_cmp_copy(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const CacheViewMut& dst,
                               hipStream_t);
 kvtrim_status launch_occupancy(kvtrim_ctx*, const CacheView&, const int32_t* now, double* occ, hipStream_t);
 void launch_cmp_scan(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const int32_t* kept,
                      const CacheViewMut& dst, int32_t reserve, hipStream_t);
-bool launch_attn_fused(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const CacheViewMut& dst, const uint16_t* q,
-                       int32_t layer_begin, int32_t layer_end, float scale, hipStream_t st);
-bool launch_attn_fused_inplace(kvtrim_ctx*, const CacheViewMut& c, const uint8_t* keep, const CacheViewMut& stage,
-                               const uint16_t* q, int32_t layer_begin, int32_t layer_end, float scale, hipStream_t st);
 kvtrim_status launch_combine(kvtrim_ctx*, const int32_t* chunk_prefix, int32_t layer_begin, int32_t layer_end,
                              float* out, float* lse, hipStream_t);
-void launch_cmp_scan_inplace(kvtrim_ctx*, const CacheViewMut& c, const uint8_t* keep, const int32_t* kept, int32_t run, hipStream_t);
+void launch_cmp_scan_inplace(kvtrim_ctx*, const CacheViewMut& c, const uint8_t* keep, const int32_t* kept, hipStream_t);
 // Stage 3 alone inside the cache itself.
 kvtrim_status launch_compact_inplace(kvtrim_ctx*, const CacheViewMut& c, const uint8_t* keep, const int32_t* kept,
                                      const CacheViewMut& stage, hipStream_t);

@@ -42,7 +42,7 @@ def test_llama_32k_whole():
 @pytest.mark.parametrize("name", ["llama", "vlm"])
 def test_steady_state_in_place_whole(name):
     # the first eviction goes out of place into a cache with four free slots per segment, the next three steps are
-    # compacted inside it (llama: G = 4, the one-shot kernel's instance; vlm: G = 7, the loop-shaped one)
+    # compacted inside it (llama: G = 4; vlm: G = 7)
     w = ki.workload(name)
     pre = {k: (v.cpu() if torch.is_tensor(v) else v) for k, v in ki.prefill_cache(w, reserve=4, device=DEV).items()}
     res = run_steps_inplace_both(w, 4, w.budget, 4, pre, [t - 1 for t in w.prefill], device=DEV, rebalance_at=(0,))

@@ -220,9 +220,9 @@ def test_horizon_tail_must_be_consistent_between_caches():
 @pytest.mark.parametrize("roomy", [True, False])
 def test_fused_call_with_a_layer_range_and_sparse_mask(roomy, G, D):
     # compaction + attention in one call on a mask that keeps about one entry in five, layers [1, 3) only.  With a
-    # destination of at least a quarter of the source a fused kernel runs (the one-shot one for small groups of query
-    # heads, the loop-shaped one for G = 8 at head_dim 128 and G = 6 at head_dim 64); with a tight one the library
-    # expects few survivors and runs the two stages one after the other - same results either way.
+    # destination of at least a quarter of the source the fused kernel works a block per chunk of the source; with a
+    # tight one the library expects few survivors and works a block per chunk of the destination - same results
+    # either way.
     w = wl(2, 3, 2, G, D)
     rng = np.random.default_rng(21)
     seg_len = rng.integers(0, 2500, w.nseg)
