@@ -21,6 +21,7 @@ constexpr int ATT_THREADS = 256;
 typedef __attribute__((ext_vector_type(4))) float float4v;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) short short4v;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
 __global__ __launch_bounds__(1024) void k_att_plan(CacheView c, Shape sh, Workspace ws, int chunk,
                                                    int layer_begin, int layer_end, int64_t max_chunks) {
@@ -55,6 +56,7 @@ struct Frag<128> {
         f[6] = __uint_as_float(x.w << 16); f[7] = __uint_as_float(x.w & 0xffff0000u);
     }
     static __device__ __forceinline__ vec zero() { return make_uint4(0, 0, 0, 0); }
+    static __device__ __forceinline__ unsigned word(vec x, int w) { return w == 0 ? x.x : (w == 1 ? x.y : (w == 2 ? x.z : x.w)); }
 };
 template <>
 struct Frag<64> {
@@ -68,6 +70,7 @@ struct Frag<64> {
         f[2] = __uint_as_float(x.y << 16); f[3] = __uint_as_float(x.y & 0xffff0000u);
     }
     static __device__ __forceinline__ vec zero() { return make_uint2(0, 0); }
+    static __device__ __forceinline__ unsigned word(vec x, int w) { return w == 0 ? x.x : x.y; }
 };
 
 template <int G, int E, int QI>
@@ -106,7 +109,8 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
     constexpr int E = F::E;
     constexpr int NSTREAM = ATT_THREADS / 64;
     __shared__ float s_m[NSTREAM][G], s_l[NSTREAM][G];
-    __shared__ float s_o[NSTREAM][G][D];
+    constexpr int SO = D + 8;                                     // a 32-byte skew between heads
+    __shared__ __attribute__((aligned(16))) float s_o[NSTREAM][G][SO];
 
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int ch = blockIdx.x;                                    // (the grid never exceeds the tables)
@@ -129,12 +133,11 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
     for (int j = 0; j < 4; ++j)
         qf[j] = c16 < G ? reinterpret_cast<const vec*>(q + qrow * D)[4 * j + b4] : F::zero();
 
-    float o[G][E];
+    // o[e][i] = unnormalised output of head c16, column E (4 b4 + i) + e (the MFMA accumulators of P.V)
+    float4v o[E];
 #pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int e = 0; e < E; ++e) o[g][e] = 0.f;
-    float m = -INFINITY, l = 0.f;
+    for (int e = 0; e < E; ++e) o[e] = float4v{0.f, 0.f, 0.f, 0.f};
+    float m = -INFINITY, l = 0.f;                                 // m: running maximum of head c16 (the same in the four row groups)
     const int t_now = SOFT ? now[seq] : 0;
 
     const vec* kp = reinterpret_cast<const vec*>(c.k);
@@ -192,6 +195,8 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
             z[i] = valid ? zi : -INFINITY;
             tmax = fmaxf(tmax, z[i]);
         }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));             // over the tile's 16 rows: P.V sums over all of them
         const float m_new = fmaxf(m, tmax);
         const float m_safe = m_new == -INFINITY ? 0.f : m_new;
         const float alpha = __builtin_amdgcn_exp2f(m - m_safe);   // m = -inf gives 0; l and o are 0 then
@@ -202,50 +207,59 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
             p[i] = __builtin_amdgcn_exp2f(z[i] - m_safe);
             psum += p[i];
         }
-        l = l * alpha + psum;
+        l = l * alpha + psum;                                     // (this row group's share; summed over the groups at the end)
         m = m_new;
-        if (__any(alpha != 1.0f)) PV<G, E, 0>::scale(o, alpha);
+        if (__any(alpha != 1.0f)) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            float vfl[E];
-            F::unpack(vf[i], vfl);
-            PV<G, E, 0>::run(o, p[i], vfl);
+            for (int e = 0; e < E; ++e) o[e] *= alpha;
+        }
+        // P.V on the matrix cores: lane (b4, c16) holds, for every column of its slice, the values of its 4 rows - 4
+        // consecutive slots of the reduction dimension of a 16x16x32 MFMA with m = the column block c16 - and the
+        // probabilities of the same rows for head c16, the other operand (n = c16).  A probability goes in as two
+        // bf16 terms, the rounded value (slots 0..3) and the rounded remainder (slots 4..7, against the same V values
+        // again), so every product is exact to 2^-16; the sums are fp32.  One MFMA per column of the slice.
+        const bf16x2 h01 = {(__bf16)p[0], (__bf16)p[1]}, h23 = {(__bf16)p[2], (__bf16)p[3]};
+        const bf16x2 l01 = {(__bf16)(p[0] - (float)h01.x), (__bf16)(p[1] - (float)h01.y)};
+        const bf16x2 l23 = {(__bf16)(p[2] - (float)h23.x), (__bf16)(p[3] - (float)h23.y)};
+        const uint4 pb = make_uint4(__builtin_bit_cast(unsigned, h01), __builtin_bit_cast(unsigned, h23),
+                                    __builtin_bit_cast(unsigned, l01), __builtin_bit_cast(unsigned, l23));
+#pragma unroll
+        for (int w = 0; w < E / 2; ++w) {
+            const unsigned x0 = F::word(vf[0], w), x1 = F::word(vf[1], w), x2 = F::word(vf[2], w), x3 = F::word(vf[3], w);
+            // columns 2 w (low halves) and 2 w + 1 (high halves) of the four rows
+            const unsigned a01 = __builtin_amdgcn_perm(x1, x0, 0x05040100u), a23 = __builtin_amdgcn_perm(x3, x2, 0x05040100u);
+            const unsigned b01 = __builtin_amdgcn_perm(x1, x0, 0x07060302u), b23 = __builtin_amdgcn_perm(x3, x2, 0x07060302u);
+            o[2 * w] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, make_uint4(a01, a23, a01, a23)),
+                                                               __builtin_bit_cast(bf16x8, pb), o[2 * w], 0, 0, 0);
+            o[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, make_uint4(b01, b23, b01, b23)),
+                                                                   __builtin_bit_cast(bf16x8, pb), o[2 * w + 1], 0, 0, 0);
         }
     }
 
-    // merge the four row-group streams of the wavefront (lanes xor 16, xor 32), then the four
-    // wavefronts of the block through LDS
-    float m_all = fmaxf(m, __shfl_xor(m, 16, 64));
-    m_all = fmaxf(m_all, __shfl_xor(m_all, 32, 64));
-    const float m_fin = m_all == -INFINITY ? 0.f : m_all;
-    const float wgt = __builtin_amdgcn_exp2f(m - m_fin);          // 0 for a stream that saw no row
-    float l_all = l * wgt;
+    // the wavefront's partial (the MFMAs have summed over its row groups already) goes to LDS, where the four
+    // wavefronts of the block are merged: s_o[wave][head][(4 i + b4) E + e] = column E (4 b4 + i) + e
+    float l_all = l;
     l_all += __shfl_xor(l_all, 16, 64);
     l_all += __shfl_xor(l_all, 32, 64);
-    PV<G, E, 0>::scale(o, wgt);
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int e = 0; e < E; ++e) {
-            float x = o[g][e];
-            x += __shfl_xor(x, 16, 64);
-            x += __shfl_xor(x, 32, 64);
-            o[g][e] = x;
-        }
-    if (b4 == 0) {
-        if (c16 < G) {
-            s_m[wave][c16] = m_all;
+    if (c16 < G) {
+        if (b4 == 0) {
+            s_m[wave][c16] = m;
             s_l[wave][c16] = l_all;
         }
 #pragma unroll
-        for (int g = 0; g < G; ++g)
+        for (int i = 0; i < 4; ++i) {
+            float* so = &s_o[wave][c16][(4 * i + b4) * E];
 #pragma unroll
-            for (int e = 0; e < E; ++e) s_o[wave][g][c16 * E + e] = o[g][e];
+            for (int e4 = 0; e4 < E; e4 += 4)
+                *reinterpret_cast<float4*>(so + e4) = make_float4(o[e4][i], o[e4 + 1][i], o[e4 + 2][i], o[e4 + 3][i]);
+        }
     }
     __syncthreads();
     float* part = ws.att_partial + (size_t)ch * G * (D + 2);
     for (int idx = tid; idx < G * D; idx += ATT_THREADS) {
         const int g = idx / D, d = idx % D;
+        const int cb = d / E;
+        const int so_at = (4 * (cb & 3) + (cb >> 2)) * E + d % E;
         float M = -INFINITY;
 #pragma unroll
         for (int s = 0; s < NSTREAM; ++s) M = fmaxf(M, s_m[s][g]);
@@ -254,7 +268,7 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
 #pragma unroll
         for (int s = 0; s < NSTREAM; ++s) {
             const float w = __builtin_amdgcn_exp2f(s_m[s][g] - Ms);
-            accd += s_o[s][g][d] * w;
+            accd += s_o[s][g][so_at] * w;
             lsum += s_l[s][g] * w;
         }
         part[g * (D + 2) + 2 + d] = accd;
