@@ -5,13 +5,14 @@
 //   Q.K^T  one MFMA 16x16 accumulator per tile (rows = 16 keys, columns = the G query heads,
 //          padded to 16); K fragments are loaded straight from HBM in the operand layout
 //          (lane = key row, four lanes share 64 contiguous bytes of the row).
-//   P.V    vector FMAs: a lane owns one 16-byte column slice of the row, so V is read fully
-//          coalesced (16 lanes = one 256-byte row) and the probability of (query, row) is
-//          fetched from its accumulator lane with a DPP row broadcast.
-// Each 16-lane row group of a wavefront is an independent online-softmax stream (rows
-// 4b..4b+3 of every tile); at the end of the chunk the four streams of a wavefront are merged
-// with lane shuffles, the four wavefronts through LDS, and the chunks of a segment by
-// k_att_combine.  Logits are kept in base-2 units.
+//   P.V    one MFMA 16x16x32 per column of a lane's slice: a lane owns one 16-byte column slice of
+//          4 rows of the tile (rows 4b..4b+3 for its row group b), so V is read fully coalesced
+//          (16 lanes = one 256-byte row) and the lane holds, per column, 4 consecutive slots of
+//          the MFMA's reduction dimension; the probabilities of those rows for query head c are
+//          what the Q.K^T accumulator of lane (b, c) holds - the other operand, as two bf16 terms.
+// A wavefront keeps one online-softmax stream per query head (the maximum over the tile's 16
+// rows); at the end of the chunk the four wavefronts are merged through LDS, and the chunks of
+// a segment by k_att_combine.  Logits are kept in base-2 units.
 #include "kvtrim_device.h"
 
 namespace kvtrim {
@@ -34,12 +35,6 @@ __global__ __launch_bounds__(1024) void k_att_plan(CacheView c, Shape sh, Worksp
                       ws.att_desc, max_chunks, nullptr, ws.err);
 }
 
-// broadcast lane `Q` of every 16-lane row to the whole row
-template <int Q>
-__device__ __forceinline__ float row_bcast(float x) {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x150 + Q, 0xF, 0xF, false));
-}
-
 template <int D>
 struct Frag;
 template <>
@@ -48,12 +43,6 @@ struct Frag<128> {
     static constexpr int E = 8;
     static __device__ __forceinline__ float4v mma(vec a, vec b, float4v c) {
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    }
-    static __device__ __forceinline__ void unpack(vec x, float* f) {
-        f[0] = __uint_as_float(x.x << 16); f[1] = __uint_as_float(x.x & 0xffff0000u);
-        f[2] = __uint_as_float(x.y << 16); f[3] = __uint_as_float(x.y & 0xffff0000u);
-        f[4] = __uint_as_float(x.z << 16); f[5] = __uint_as_float(x.z & 0xffff0000u);
-        f[6] = __uint_as_float(x.w << 16); f[7] = __uint_as_float(x.w & 0xffff0000u);
     }
     static __device__ __forceinline__ vec zero() { return make_uint4(0, 0, 0, 0); }
     static __device__ __forceinline__ unsigned word(vec x, int w) { return w == 0 ? x.x : (w == 1 ? x.y : (w == 2 ? x.z : x.w)); }
@@ -65,33 +54,8 @@ struct Frag<64> {
     static __device__ __forceinline__ float4v mma(vec a, vec b, float4v c) {
         return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(short4v, a), __builtin_bit_cast(short4v, b), c, 0, 0, 0);
     }
-    static __device__ __forceinline__ void unpack(vec x, float* f) {
-        f[0] = __uint_as_float(x.x << 16); f[1] = __uint_as_float(x.x & 0xffff0000u);
-        f[2] = __uint_as_float(x.y << 16); f[3] = __uint_as_float(x.y & 0xffff0000u);
-    }
     static __device__ __forceinline__ vec zero() { return make_uint2(0, 0); }
     static __device__ __forceinline__ unsigned word(vec x, int w) { return w == 0 ? x.x : x.y; }
-};
-
-template <int G, int E, int QI>
-struct PV {   // o[QI..G) += bcast(p, q) * v
-    static __device__ __forceinline__ void run(float (&o)[G][E], float p, const float* vf) {
-        const float pb = row_bcast<QI>(p);
-#pragma unroll
-        for (int e = 0; e < E; ++e) o[QI][e] = fmaf(pb, vf[e], o[QI][e]);
-        PV<G, E, QI + 1>::run(o, p, vf);
-    }
-    static __device__ __forceinline__ void scale(float (&o)[G][E], float a) {
-        const float ab = row_bcast<QI>(a);
-#pragma unroll
-        for (int e = 0; e < E; ++e) o[QI][e] *= ab;
-        PV<G, E, QI + 1>::scale(o, a);
-    }
-};
-template <int G, int E>
-struct PV<G, E, G> {
-    static __device__ __forceinline__ void run(float (&)[G][E], float, const float*) {}
-    static __device__ __forceinline__ void scale(float (&)[G][E], float) {}
 };
 
 // partial layout: [chunk][G][D + 2] = (m in base-2 units, l, o[D] unnormalised)

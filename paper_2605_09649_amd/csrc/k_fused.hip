@@ -12,12 +12,13 @@
 // loads and one batch of stores, four rows per instruction (16 lanes x 16 bytes = one
 // 256-byte row, so loads and stores are whole rows), and ends - short-lived wavefronts
 // measured ~10 % faster on this chip than wavefronts that loop over several batches.  In
-// that layout a lane owns the same 8-element column slice of the K row and of the V row:
-//   q.k   8 FMAs per query head and lane, then a 16-lane all-reduce with DPP
-//   p.v   8 FMAs per query head and lane, no cross-lane traffic
-// Each 16-lane row group computes a softmax partial over its 4 rows; the four row groups of
-// a wavefront are merged with lane shuffles, the wavefronts of the block through LDS, and
-// the chunks of a segment by k_att_combine.
+// that layout a lane owns the same 8-element column slice of the K rows and of the V rows of 4 rows:
+//   q.k   4 packed two-element bf16 dot products per query head, row and lane, then a 16-lane
+//         all-reduce with DPP
+//   p.v   one MFMA per column of the slice: the lane's 4 rows are 4 consecutive slots of the
+//         reduction dimension, and the MFMA sums over the wavefront's 16 rows for all query heads
+// A wavefront takes one softmax partial per query head over its 16 rows; the wavefronts of the
+// block are merged through LDS, and the chunks of a segment by k_att_combine.
 //
 // The same kernel has an instance that compacts INSIDE the cache (segments keep their starts; only the rows
 // behind an eviction move), followed by k_cmp_unstage; k_cmp_move_inplace is that instance without the
@@ -53,12 +54,6 @@ struct Row<128> {
         v4u t = {v.x, v.y, v.z, v.w};
         __builtin_nontemporal_store(t, reinterpret_cast<v4u*>(p));
     }
-    static __device__ __forceinline__ void unpack(vec x, float* f) {
-        f[0] = __uint_as_float(x.x << 16); f[1] = __uint_as_float(x.x & 0xffff0000u);
-        f[2] = __uint_as_float(x.y << 16); f[3] = __uint_as_float(x.y & 0xffff0000u);
-        f[4] = __uint_as_float(x.z << 16); f[5] = __uint_as_float(x.z & 0xffff0000u);
-        f[6] = __uint_as_float(x.w << 16); f[7] = __uint_as_float(x.w & 0xffff0000u);
-    }
     static __device__ __forceinline__ unsigned word(vec x, int w) { return w == 0 ? x.x : (w == 1 ? x.y : (w == 2 ? x.z : x.w)); }
     static __device__ __forceinline__ float dot(vec a, vec b) {   // the lane's 8-element slice of q . k
         return dot2_bf16(a.w, b.w, dot2_bf16(a.z, b.z, dot2_bf16(a.y, b.y, dot2_bf16(a.x, b.x, 0.f))));
@@ -75,10 +70,6 @@ struct Row<64> {
     static __device__ __forceinline__ void st(vec* p, vec v) {
         v2u t = {v.x, v.y};
         __builtin_nontemporal_store(t, reinterpret_cast<v2u*>(p));
-    }
-    static __device__ __forceinline__ void unpack(vec x, float* f) {
-        f[0] = __uint_as_float(x.x << 16); f[1] = __uint_as_float(x.x & 0xffff0000u);
-        f[2] = __uint_as_float(x.y << 16); f[3] = __uint_as_float(x.y & 0xffff0000u);
     }
     static __device__ __forceinline__ unsigned word(vec x, int w) { return w == 0 ? x.x : x.y; }
     static __device__ __forceinline__ float dot(vec a, vec b) { return dot2_bf16(a.y, b.y, dot2_bf16(a.x, b.x, 0.f)); }
