@@ -411,6 +411,20 @@ class Runner:
             kv.kvtrim_paged_attn(ctx, pc, inp["q"], 0, w.n_layers, scale, out, lse)
             return
         cur = self.cur
+        if a.inplace and not (a.unfused or a.separate_score_select or a.separate_calls) and s > 0:
+            # the whole step in one call, inside the cache (four kernels) or - every ROOM-th step - out of place
+            new = (inp["k_new"], inp["v_new"], inp["log_beta_new"], self.pos_news[s], 1, self.nows[s], self.budget, self.score,
+                   self.keep, self.kept)
+            dst = self.spare[self.flip]
+            if s % a.inplace:
+                kv.kvtrim_decode_step_inplace(ctx, cur, *new, dst, inp["q"], 0, w.n_layers, scale, out, lse, thr_key_out=self.thr,
+                                              log_tail_new=inp.get("log_tail_new"), evict_hint=self.per_seq)
+            else:
+                kv.kvtrim_decode_step(ctx, cur, *new, dst, self.reserve, inp["q"], 0, w.n_layers, scale, out, lse,
+                                      thr_key_out=self.thr, log_tail_new=inp.get("log_tail_new"), evict_hint=self.per_seq)
+                self.cur = dst
+                self.flip ^= 1
+            return
         if not (a.paged or a.inplace or a.unfused or a.separate_score_select or a.separate_calls):
             # the whole step in one call (three kernels for a decode step; the first step, with hint 0, runs the
             # calls it stands for one after the other)
@@ -674,6 +688,9 @@ def run_decode(args, brief=False):
                f"compact_attn_inplace (stages 3+4 fused inside the cache, {args.inplace} free slots per segment; every "
                f"{args.inplace}th step an out-of-place compact_attn)" if args.inplace else
                "compact_attn (stages 3+4 fused)")))
+    if args.inplace and not (args.paged or args.unfused or args.separate_score_select or args.separate_calls):
+        calls = (f"decode_step_inplace (append, stages 1-4 in one call, stages 3+4 inside the cache: four kernels per decode step; "
+                 f"{args.inplace} free slots per segment, every {args.inplace}th step an out-of-place decode_step)")
     result = {
         "metric": metric_name(w),
         "value": 1e3 / ms_per_step,
@@ -812,7 +829,7 @@ def run_decode(args, brief=False):
                                                 "select_compact_bit_exact": ok, "attn_max_norm_rel_err": chk["attn_err"]}
         next_step += cpu_steps
 
-    # ---- the same steps with stages 3+4 done inside the cache (kvtrim_compact_attn_inplace), timed beside the metric's
+    # ---- the same steps with stages 3+4 done inside the cache (kvtrim_decode_step_inplace), timed beside the metric's
     # out-of-place step: ROOM free slots behind every segment, every ROOM-th step out of place to even them out (at
     # least one such step falls inside the timed steps); the last step is checked against the oracle
     K2 = min(K, 128)
@@ -834,13 +851,13 @@ def run_decode(args, brief=False):
         def step_room(i, in_place):
             nonlocal cur, other
             inp = extra[i]
-            kv.kvtrim_append(ctx, cur, inp["k_new"], inp["v_new"], inp["log_beta_new"], extra_pos[i], 1,
-                             log_tail_new=inp.get("log_tail_new"))
-            kv.kvtrim_score_select(ctx, cur, extra_now[i], r.budget, r.score, r.keep, r.kept, r.thr, evict_hint=per_seq)
+            new = (inp["k_new"], inp["v_new"], inp["log_beta_new"], extra_pos[i], 1, extra_now[i], r.budget, r.score, r.keep, r.kept)
             if in_place:
-                kv.kvtrim_compact_attn_inplace(ctx, cur, r.keep, r.kept, other, inp["q"], 0, w.n_layers, r.scale, r.out, r.lse)
+                kv.kvtrim_decode_step_inplace(ctx, cur, *new, other, inp["q"], 0, w.n_layers, r.scale, r.out, r.lse,
+                                              thr_key_out=r.thr, log_tail_new=inp.get("log_tail_new"), evict_hint=per_seq)
             else:
-                kv.kvtrim_compact_attn(ctx, cur, r.keep, r.kept, other, ROOM, inp["q"], 0, w.n_layers, r.scale, r.out, r.lse)
+                kv.kvtrim_decode_step(ctx, cur, *new, other, ROOM, inp["q"], 0, w.n_layers, r.scale, r.out, r.lse,
+                                      thr_key_out=r.thr, log_tail_new=inp.get("log_tail_new"), evict_hint=per_seq)
                 cur, other = other, (big[1] if other is big[0] else big[0])
 
         step_room(0, False)                                        # into a cache with room behind every segment
@@ -876,8 +893,8 @@ def run_decode(args, brief=False):
         result["in_place_variant"] = {
             "ms_per_step": ms_room, "value": 1e3 / ms_room, "unit": "steps/s", "steps": K2 - 1, "room": ROOM,
             "out_of_place_steps_in_timed_region": n_oop, "parity_on_last_step": parity_ip,
-            "what": "append, score_select, compact_attn_inplace: a row moves only if an entry before it in its segment was evicted; "
-                    f"every {ROOM}th step is an out-of-place compact_attn that evens the free slots out"}
+            "what": "kvtrim_decode_step_inplace (four kernels per decode step): a row moves only if an entry before it in its "
+                    f"segment was evicted; every {ROOM}th step is an out-of-place kvtrim_decode_step that evens the free slots out"}
         del big, extra
     del r
     gc.collect()

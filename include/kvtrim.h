@@ -278,8 +278,8 @@ kvtrim_status kvtrim_append(kvtrim_ctx *ctx, kvtrim_cache *c, const void *k_new,
  *     -> kvtrim_compact_attn(src -> dst, reserve, q)
  * leave there (bit for bit in everything but out / lse, which agree within the attention tolerance: the split of
  * the softmax sums is the same, so in practice they are equal too).  Arguments as in those three calls; keep_out is
- * required.  With a small evict_hint (see kvtrim_score_select) and up to 5 query heads per KV head (4 at head_dim
- * 64), at most 1024 segments per sequence, 1024 sequences and 16 new tokens per segment the step is THREE kernels:
+ * required.  With a small evict_hint (see kvtrim_score_select), at most 1024 segments per sequence, 1024 sequences
+ * and 16 new tokens per segment the step is THREE kernels:
  * one scores, lists the eviction candidates and - in each sequence's last block - ranks them, counts the evicted
  * entries per segment and per chunk of 128 entries and leaves the destination's segment table and, per segment, the
  * indices of its evicted entries (further blocks of the same launch append the new tokens); one moves every
@@ -293,6 +293,21 @@ kvtrim_status kvtrim_decode_step(kvtrim_ctx *ctx, kvtrim_cache *src, const void 
                                  uint8_t *keep_out, int32_t *kept_out, uint32_t *thr_key_out, kvtrim_cache *dst,
                                  int32_t reserve, const void *q, int32_t layer_begin, int32_t layer_end,
                                  float softmax_scale, float *out, float *lse, int64_t evict_hint, void *hip_stream);
+
+/* The same decode step with stages 3 + 4 done INSIDE the cache (Sec. 4.2).  Leaves in c, score_out, keep_out,
+ * kept_out, thr_key_out, out and lse exactly what
+ *     kvtrim_append(c, new tokens) -> kvtrim_score_select(c, now, budget, evict_hint)
+ *     -> kvtrim_compact_attn_inplace(c, spare, q)
+ * leave there; arguments and the rules for `spare` as in those calls (every segment needs free slots for its new
+ * tokens behind it: kvtrim_min_room).  Under the conditions of kvtrim_decode_step it is FOUR kernels: the scoring
+ * kernel leaves every segment's start where it is, the row mover touches only the rows behind an eviction, a small
+ * kernel puts the rows it had to park in `spare` in place, and one merges the partial attention results. */
+kvtrim_status kvtrim_decode_step_inplace(kvtrim_ctx *ctx, kvtrim_cache *c, const void *k_new, const void *v_new,
+                                         const float *log_beta_new, const float *log_tail_new, const int32_t *pos_new,
+                                         int32_t n_new, const int32_t *now, const int64_t *budget, float *score_out,
+                                         uint8_t *keep_out, int32_t *kept_out, uint32_t *thr_key_out, kvtrim_cache *spare,
+                                         const void *q, int32_t layer_begin, int32_t layer_end, float softmax_scale,
+                                         float *out, float *lse, int64_t evict_hint, void *hip_stream);
 
 /* A chunk of a prefill on the ragged layout in one call (the multi-turn flow of Sec. 4.2 / Sec. 5:
  * after every appended chunk of tokens the cache is rescored, selected and compacted).  Leaves in

@@ -12,7 +12,7 @@ from .binding import (PAGE_SIZE, Cache, Context, Gate, KvtrimError, PagedCache, 
                       kvtrim_occupancy, kvtrim_paged_append, kvtrim_paged_attn, kvtrim_paged_build,
                       kvtrim_paged_defrag, kvtrim_paged_evict, kvtrim_paged_score, kvtrim_paged_score_select, kvtrim_paged_decode_step, kvtrim_paged_select, kvtrim_poll_error,
                       kvtrim_profile_begin, kvtrim_profile_end, kvtrim_score, kvtrim_select_global,
-                      kvtrim_select_global_noalloc, kvtrim_score_select, kvtrim_select_path_counts, kvtrim_decode_step,
+                      kvtrim_select_global_noalloc, kvtrim_score_select, kvtrim_select_path_counts, kvtrim_decode_step, kvtrim_decode_step_inplace,
                       kvtrim_workspace_bytes, library_path, load_library)
 
 __all__ = ["PAGE_SIZE", "Cache", "Context", "Gate", "KvtrimError", "PagedCache", "kvtrim_gate_forward",
@@ -22,5 +22,5 @@ __all__ = ["PAGE_SIZE", "Cache", "Context", "Gate", "KvtrimError", "PagedCache",
            "kvtrim_occupancy", "kvtrim_paged_append", "kvtrim_paged_attn", "kvtrim_paged_build",
            "kvtrim_paged_defrag", "kvtrim_paged_evict", "kvtrim_paged_score", "kvtrim_paged_score_select", "kvtrim_paged_decode_step", "kvtrim_paged_select", "kvtrim_poll_error",
            "kvtrim_profile_begin", "kvtrim_profile_end", "kvtrim_score", "kvtrim_select_global",
-           "kvtrim_select_global_noalloc", "kvtrim_score_select", "kvtrim_select_path_counts", "kvtrim_decode_step",
+           "kvtrim_select_global_noalloc", "kvtrim_score_select", "kvtrim_select_path_counts", "kvtrim_decode_step", "kvtrim_decode_step_inplace",
            "kvtrim_workspace_bytes", "library_path", "load_library"]

@@ -13,7 +13,7 @@ STATUS = {0: "KVTRIM_OK", -1: "KVTRIM_EINVAL", -2: "KVTRIM_ENOMEM", -3: "KVTRIM_
 
 EXPORTS = ["kvtrim_create", "kvtrim_destroy", "kvtrim_workspace_bytes", "kvtrim_last_error",
            "kvtrim_poll_error", "kvtrim_score", "kvtrim_select_global", "kvtrim_score_select", "kvtrim_select_path_counts", "kvtrim_compact",
-           "kvtrim_decode_attn", "kvtrim_decode_attn_soft", "kvtrim_occupancy", "kvtrim_compact_attn", "kvtrim_min_room", "kvtrim_compact_inplace", "kvtrim_compact_attn_inplace", "kvtrim_append", "kvtrim_append_compact", "kvtrim_decode_step",
+           "kvtrim_decode_attn", "kvtrim_decode_attn_soft", "kvtrim_occupancy", "kvtrim_compact_attn", "kvtrim_min_room", "kvtrim_compact_inplace", "kvtrim_compact_attn_inplace", "kvtrim_append", "kvtrim_append_compact", "kvtrim_decode_step", "kvtrim_decode_step_inplace",
            "kvtrim_paged_build", "kvtrim_paged_append", "kvtrim_paged_score", "kvtrim_paged_select", "kvtrim_paged_score_select", "kvtrim_paged_decode_step",
            "kvtrim_paged_evict", "kvtrim_paged_defrag", "kvtrim_paged_attn", "kvtrim_gate_scratch_bytes", "kvtrim_gate_forward", "kvtrim_gate_prepared_bytes", "kvtrim_gate_prepare",
            "kvtrim_gate_forward_prepared",
@@ -102,6 +102,10 @@ def load_library():
                                            C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                            C.c_void_p, C.POINTER(_Cache), C.c_int32, C.c_void_p, C.c_int32, C.c_int32,
                                            C.c_float, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        lib.kvtrim_decode_step_inplace.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                   C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                   C.c_void_p, C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_int32, C.c_int32,
+                                                   C.c_float, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         P = C.POINTER(_PagedCache)
         lib.kvtrim_paged_build.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_void_p, P, C.c_void_p]
         lib.kvtrim_paged_append.argtypes = [C.c_void_p, P, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -400,6 +404,18 @@ def kvtrim_decode_step(ctx, src, k_new, v_new, log_beta_new, pos_new, n_new, now
         _ptr(kept_out, torch.int32), _ptr(thr_key_out), C.byref(dst.c), int(reserve), _ptr(q, torch.bfloat16),
         int(layer_begin), int(layer_end), float(softmax_scale), _ptr(out, torch.float32), _ptr(lse, torch.float32),
         int(evict_hint), _stream(stream)), "kvtrim_decode_step")
+
+
+def kvtrim_decode_step_inplace(ctx, cache, k_new, v_new, log_beta_new, pos_new, n_new, now, budget, score_out, keep_out,
+                               kept_out, spare, q, layer_begin, layer_end, softmax_scale, out, lse=None, thr_key_out=None,
+                               log_tail_new=None, evict_hint=0, stream=None):
+    _check(ctx, load_library().kvtrim_decode_step_inplace(
+        ctx.handle, C.byref(cache.c), _ptr(k_new, torch.bfloat16), _ptr(v_new, torch.bfloat16),
+        _ptr(log_beta_new, torch.float32), _ptr(log_tail_new, torch.float32), _ptr(pos_new, torch.int32), int(n_new),
+        _ptr(now, torch.int32), _ptr(budget, torch.int64), _ptr(score_out, torch.float32), _ptr(keep_out, torch.uint8),
+        _ptr(kept_out, torch.int32), _ptr(thr_key_out), C.byref(spare.c), _ptr(q, torch.bfloat16),
+        int(layer_begin), int(layer_end), float(softmax_scale), _ptr(out, torch.float32), _ptr(lse, torch.float32),
+        int(evict_hint), _stream(stream)), "kvtrim_decode_step_inplace")
 
 
 def kvtrim_paged_build(ctx, src, keep, kept, dst, stream=None):

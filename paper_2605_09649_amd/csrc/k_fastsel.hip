@@ -490,7 +490,7 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
         if (tid == 0) {
             ws.cmp_chunk_prefix[seg] = before;
             if (seg == sh.nseg - 1) ws.cmp_chunk_prefix[sh.nseg] = before + nch;
-            ws.step_len[seg] = len;
+            if (!sa.inplace) ws.step_len[seg] = len;              // (in place: the sequence's last block leaves the survivors' count there)
         }
         return;
     }
@@ -658,7 +658,7 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
         // (write-through: the counts are added with device-scope atomics) complete while the candidates are ranked.
         if (tid < sh.segs_per_seq) my_len = s_pool[FAST_STAGE + tid];
         step_cex = block_excl_scan<int32_t>((my_len + CMP_CHUNK - 1) / CMP_CHUNK, sm.lds32, &step_ctot);
-        if (step_total <= sa.dst.cap)
+        if (sa.inplace || step_total <= sa.dst.cap)
             for (int i = tid; i < step_ctot; i += FAST_THREADS) st_dev(&ws.step_chunk_ev[step_chunks_before + i], 0u);
         cnt = s_seqcnt[seq];
         __syncthreads();
@@ -849,7 +849,7 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
     // offset per chunk of 128 entries (flagged when the chunk loses nothing) and the keep mask of the chunks that do
     // lose entries.  Entry (g, position p, key) survives iff it is not behind the last retained entry `out`.
     if (STEP) {
-        if (step_total > sa.dst.cap) {                            // every sequence's last block takes the same decision
+        if (!sa.inplace && step_total > sa.dst.cap) {             // every sequence's last block takes the same decision
             if (tid == 0) atomicOr(ws.err, ERR_CAP);
             return;
         }
@@ -894,10 +894,15 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
                 const int g = g0 + tid;
                 s_off[tid] = eex;
                 kept_out[g] = my_len - my_ev;
-                sa.dst.seg_start[g] = step_before + nex;
-                sa.dst.seg_len[g] = my_len - my_ev;
                 StepSegRec* rec = ws.step_rec + g;
-                rec->dst_start = step_before + nex;
+                if (sa.inplace) {                                 // the segment keeps its start; the row mover commits the new length
+                    rec->dst_start = c.seg_start[g];
+                    ws.step_len[g] = my_len - my_ev;
+                } else {
+                    sa.dst.seg_start[g] = step_before + nex;
+                    sa.dst.seg_len[g] = my_len - my_ev;
+                    rec->dst_start = step_before + nex;
+                }
                 rec->cnt = my_ev;
                 rec->off = eex;
             }
@@ -924,6 +929,7 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
             for (int g = g0; g < g0 + nsg; ++g) {
                 bool b2 = false, n2 = false;
                 const SegView v = seg_view<KIND>(c, g, sh.nseg, sa, &b2, &n2);
+                if (sa.inplace) cursor = v.start;                 // the segment keeps its start
                 int64_t running = 0;
                 for (int t0 = 0; t0 < v.len; t0 += FAST_THREADS) {   // tiles of 8 chunks
                     const int j = t0 + tid;
@@ -960,8 +966,12 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
                 }
                 if (tid == 0) {
                     kept_out[g] = (int32_t)running;
-                    sa.dst.seg_start[g] = cursor;
-                    sa.dst.seg_len[g] = (int32_t)running;
+                    if (sa.inplace) {
+                        ws.step_len[g] = (int32_t)running;
+                    } else {
+                        sa.dst.seg_start[g] = cursor;
+                        sa.dst.seg_len[g] = (int32_t)running;
+                    }
                 }
                 cursor += running + sa.reserve;
                 cb += (v.len + CMP_CHUNK - 1) / CMP_CHUNK;

@@ -90,7 +90,7 @@ __device__ __forceinline__ float row16_sum(float x) {
 // whose destination lies in an earlier chunk's range - which another block may still be reading - go to the same
 // index of `stage` instead, and k_cmp_unstage puts them in place after this kernel has ended.  Rows that do not move
 // are not written at all.
-// STEP (the one-call decode step, kvtrim_decode_step; out of place only): the tables come from the step's scoring
+// STEP (the one-call decode step, kvtrim_decode_step and its in-place form): the tables come from the step's scoring
 // kernel instead of a compaction scan - the same per-chunk descriptors, but no destination per chunk: the number of
 // entries the chunk loses and a record per segment, from which the block derives where its survivors go and, in
 // the few chunks that lose entries, which they are.  The kernel then also writes the keep mask (`keep` is the
@@ -108,7 +108,6 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
                                                           const uint16_t* __restrict__ q,
                                                           Shape sh, Workspace ws, float scale_log2,
                                                           int layer_begin, int layer_end, int32_t* step_seg_len = nullptr) {
-    static_assert(!(STEP && INPLACE), "the one-call step compacts out of place");
     static_assert(!(GATHER && (INPLACE || STEP)), "the gathering instance compacts out of place, from a keep mask");
     typedef Row<D> R;
     typedef typename R::vec vec;
@@ -156,17 +155,23 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
     // Called by whole wavefronts, for a full chunk AFTER its rows have been requested: the record comes with one
     // vector load of 16 lanes - vector loads return in order, so the wait for the rows does not wait for it, whereas
     // a scalar load would make every later scalar wait, and the row requests behind it, wait for the record.
-    auto step_place = [&]() {
+    auto step_load = [&]() {
         static_assert(sizeof(StepSegRec) == 64 && STEP_REC_IDX == 12, "one word per lane: dst_start, cnt, off, twelve indices");
         const int32_t* rw = reinterpret_cast<const int32_t*>(ws.step_rec + cd.seg);
         step_recw = lane < 16 ? rw[lane] : 0;
         step_idx0 = (int)(sbase - src.seg_start[cd.seg]);
+    };
+    auto step_resolve = [&]() {
         step_cnt = __builtin_amdgcn_readlane(step_recw, 2);
         const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane(step_recw, 0), hi = (uint32_t)__builtin_amdgcn_readlane(step_recw, 1);
         step_more = ws.step_evl + (size_t)(cd.seg / sh.segs_per_seq) * STEP_MAX_EVICT + __builtin_amdgcn_readlane(step_recw, 3);
         int before = __popcll(__ballot(lane >= 4 && lane < 4 + min(step_cnt, STEP_REC_IDX) && step_recw < step_idx0));
         for (int i = STEP_REC_IDX; i < step_cnt; ++i) before += step_more[i] < step_idx0;
         dbase = (int64_t)(((uint64_t)hi << 32) | lo) + step_idx0 - before;
+    };
+    auto step_place = [&]() {
+        step_load();
+        step_resolve();
     };
     // Every entry of the chunk survives (almost every chunk of a decode step): row r of the survivors is row r of
     // the chunk, so the rows are requested right away instead of after the mask has arrived and been ranked.
@@ -175,7 +180,9 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
     float md_lb = 0.f, md_lt = 0.f;
     int md_pos = 0, md_rank = tid;
     // this thread carries an entry's metadata in registers (INPLACE: not if the chunk stays as it is)
-    bool md_mine = full && tid < cd.n && !(INPLACE && dbase == sbase);
+    // (a listed chunk of an in-place STEP learns its place only after its rows have been requested: it asks for the
+    // metadata then, if it moves at all)
+    bool md_mine = full && tid < cd.n && !(INPLACE && (step_listed || dbase == sbase));
     if (full) {
         cnt = cd.n;
         if (md_mine) {
@@ -226,8 +233,6 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
         }
         __syncthreads();
     }
-    // INPLACE: nothing of this chunk moves when it loses nothing and nothing was evicted before it in its segment
-    const bool moves = !INPLACE || !(full && dbase == sbase);     // uniform over the block
 
     const int seg = cd.seg;
     const int seq = seg / sh.segs_per_seq, lh = seg % sh.segs_per_seq;
@@ -363,7 +368,21 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
         vec kk[4], vv[4];
         int srow[4];
         vec qp[G];
+        // (in place a chunk that stays writes nothing, so its record is asked for BEFORE its rows: it is there first,
+        // and the attention can start on the first rows that arrive)
+        if (step_listed && full) step_load();
         if (has_rows) fetch(kk, vv, srow, qp);
+        if (step_listed && full) step_resolve();                  // (every wavefront: the decision below is the block's)
+        // nothing of this chunk moves when it loses nothing and nothing was evicted before it in its segment
+        const bool moves = !(full && dbase == sbase);             // uniform over the block
+        if (STEP && step_listed && full && moves && tid < cd.n) {
+            md_mine = true;
+            md_lb = src.log_beta[sbase + tid];
+            if (src.log_tail) md_lt = src.log_tail[sbase + tid];
+            md_pos = src.pos[sbase + tid];
+        }
+        // STEP: the chunk's place goes into the table k_cmp_unstage reads (a compaction scan would have left it there)
+        if (STEP && step_listed && tid == 0) ws.cmp_chunk_dst[ch] = dbase | (full ? CMP_DST_FULL : 0);
         if (moves) {
             // every wavefront of the block holds its rows and metadata in registers before any of them overwrites an entry
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -708,6 +727,54 @@ kvtrim_status launch_decode_step(kvtrim_ctx* ctx, const CacheViewMut& srcm, cons
 #undef KVTRIM_CASE
             default: return KVTRIM_EINVAL;
         }
+    }
+    return launch_combine(ctx, ws.cmp_chunk_prefix, layer_begin, layer_end, out, lse, st);
+}
+
+// The decode step in one call with stages 3 + 4 inside the cache: four kernels (score + resolve, move + attend, the
+// rows parked in `stage` put in place, merge) when this is a decode step the candidate list can carry; otherwise the
+// calls it stands for, one after the other.
+kvtrim_status launch_decode_step_inplace(kvtrim_ctx* ctx, const CacheViewMut& c, const StepArgs& sa, const CacheViewMut& stage,
+                                         const int32_t* now, const int64_t* budget, float* score, int32_t* kept, uint32_t* thr,
+                                         const uint16_t* q, int32_t layer_begin, int32_t layer_end, float scale, float* out,
+                                         float* lse, int64_t evict_hint, hipStream_t st) {
+    const Shape& sh = ctx->shape;
+    const Workspace& ws = ctx->ws;
+    CacheView src;
+    src.k = c.k; src.v = c.v; src.log_beta = c.log_beta; src.pos = c.pos;
+    src.seg_start = c.seg_start; src.seg_len = c.seg_len; src.cap = c.cap; src.log_tail = c.log_tail;
+    const int64_t max_chunks = src.cap / CMP_CHUNK + sh.nseg;    // <= ws.max_att_chunks, checked by the caller
+    const bool four = evict_hint > 0 && 8 * (evict_hint + 1) <= (int64_t)ws.fl_cap && sh.segs_per_seq <= STEP_MAX_SEGS &&
+                      sh.n_seq <= STEP_MAX_SEQS && sa.n_new <= STEP_MAX_NEW && max_chunks <= ws.max_cmp_chunks;
+    if (!four) {
+        kvtrim_status rc = launch_append(ctx, c, sa.k_new, sa.v_new, sa.lb_new, sa.lt_new, sa.pos_new, sa.n_new, true, nullptr, st);
+        if (rc != KVTRIM_OK) return rc;
+        rc = launch_score_select(ctx, src, now, budget, score, sa.keep_out, kept, thr, evict_hint, st);
+        if (rc != KVTRIM_OK) return rc;
+        return launch_compact_attn_inplace(ctx, c, sa.keep_out, kept, stage, q, layer_begin, layer_end, scale, out, lse, st);
+    }
+    kvtrim_status rc = launch_step_scan(ctx, src, now, budget, score, kept, thr, sa, st);
+    if (rc != KVTRIM_OK) return rc;
+    {
+        ProfScope prof(ctx, K_CMP_ATTN, st);
+        const float scale_log2 = scale * 1.4426950408889634f;
+        const dim3 grid((unsigned)max_chunks), block(FUS_THREADS);
+        switch (sh.head_dim * 16 + sh.group) {
+#define KVTRIM_CASE(d, g) \
+    case d * 16 + g: hipLaunchKernelGGL((k_cmp_attn<d, g, true, true>), grid, block, 0, st, src, (const uint8_t*)sa.keep_out, c, stage, q, sh, ws, scale_log2, layer_begin, layer_end, c.seg_len); break;
+            KVTRIM_CASE(128, 1) KVTRIM_CASE(128, 2) KVTRIM_CASE(128, 3) KVTRIM_CASE(128, 4) KVTRIM_CASE(128, 5) KVTRIM_CASE(128, 6) KVTRIM_CASE(128, 7) KVTRIM_CASE(128, 8)
+            KVTRIM_CASE(64, 1) KVTRIM_CASE(64, 2) KVTRIM_CASE(64, 3) KVTRIM_CASE(64, 4) KVTRIM_CASE(64, 5) KVTRIM_CASE(64, 6) KVTRIM_CASE(64, 7) KVTRIM_CASE(64, 8)
+#undef KVTRIM_CASE
+            default: return KVTRIM_EINVAL;
+        }
+    }
+    {
+        ProfScope prof(ctx, K_CMP_UNSTAGE, st);
+        const dim3 grid((unsigned)((max_chunks + UNS_THREADS / 64 - 1) / (UNS_THREADS / 64)));
+        if (sh.head_dim == 128)
+            hipLaunchKernelGGL(k_cmp_unstage<128>, grid, dim3(UNS_THREADS), 0, st, c, stage, kept, sh, ws);
+        else
+            hipLaunchKernelGGL(k_cmp_unstage<64>, grid, dim3(UNS_THREADS), 0, st, c, stage, kept, sh, ws);
     }
     return launch_combine(ctx, ws.cmp_chunk_prefix, layer_begin, layer_end, out, lse, st);
 }

@@ -583,6 +583,45 @@ kvtrim_status kvtrim_decode_step(kvtrim_ctx* ctx, kvtrim_cache* src, const void*
                               layer_end, softmax_scale, out, lse, evict_hint, (hipStream_t)hip_stream);
 }
 
+kvtrim_status kvtrim_decode_step_inplace(kvtrim_ctx* ctx, kvtrim_cache* c, const void* k_new, const void* v_new,
+                                         const float* log_beta_new, const float* log_tail_new, const int32_t* pos_new,
+                                         int32_t n_new, const int32_t* now, const int64_t* budget, float* score_out,
+                                         uint8_t* keep_out, int32_t* kept_out, uint32_t* thr_key_out, kvtrim_cache* spare,
+                                         const void* q, int32_t layer_begin, int32_t layer_end, float softmax_scale,
+                                         float* out, float* lse, int64_t evict_hint, void* hip_stream) {
+    if (!ctx) return KVTRIM_EINVAL;
+    if (!now || !budget || !score_out || !keep_out || !kept_out)
+        return invalid(ctx, "now / budget / score_out / keep_out / kept_out is NULL");
+    if (const char* p = inplace_problem(ctx, c, keep_out, kept_out, spare)) return invalid(ctx, p);
+    if (!k_new || !v_new || !log_beta_new || !pos_new) return invalid(ctx, "a new-token pointer is NULL");
+    if ((((uintptr_t)k_new) | ((uintptr_t)v_new)) & 15) return invalid(ctx, "k_new / v_new not 16-byte aligned");
+    if (n_new < 1) return invalid(ctx, "n_new < 1");
+    if ((c->log_tail == nullptr) != (log_tail_new == nullptr))
+        return invalid(ctx, "log_tail_new is required exactly when the cache carries log_tail");
+    if (!q || !out) return invalid(ctx, "q / out is NULL");
+    if (((uintptr_t)q) & 15) return invalid(ctx, "q not 16-byte aligned");
+    if (layer_begin < 0 || layer_end > ctx->cfg.n_layers || layer_begin >= layer_end)
+        return invalid(ctx, "empty or out-of-range layer range");
+    if (!(softmax_scale == softmax_scale)) return invalid(ctx, "softmax_scale is NaN");
+    if (c->cap_entries / CMP_CHUNK + ctx->shape.nseg > ctx->ws.max_att_chunks)
+        return invalid(ctx, "cache too large for the in-place path (more than 524288 chunks of 128 entries)");
+    StepArgs sa{};
+    sa.k_new = (const uint16_t*)k_new;
+    sa.v_new = (const uint16_t*)v_new;
+    sa.lb_new = log_beta_new;
+    sa.lt_new = log_tail_new;
+    sa.pos_new = pos_new;
+    sa.n_new = n_new;
+    sa.src = view_mut_of(c);
+    sa.dst = view_mut_of(c);
+    sa.reserve = 0;
+    sa.keep_out = keep_out;
+    sa.inplace = true;
+    return launch_decode_step_inplace(ctx, sa.src, sa, view_mut_of(spare), now, budget, score_out, kept_out, thr_key_out,
+                                      (const uint16_t*)q, layer_begin, layer_end, softmax_scale, out, lse, evict_hint,
+                                      (hipStream_t)hip_stream);
+}
+
 kvtrim_status kvtrim_append_compact(kvtrim_ctx* ctx, kvtrim_cache* src, const void* k_new, const void* v_new,
                                     const float* log_beta_new, const float* log_tail_new, const int32_t* pos_new,
                                     int32_t n_new, const int32_t* now, const int64_t* budget, float* score_out,

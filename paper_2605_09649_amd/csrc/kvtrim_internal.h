@@ -111,6 +111,7 @@ struct StepArgs {
     int reserve;
     uint8_t* keep_out;
     PagedArgs pg;
+    bool inplace;                // the compaction happens inside src (every segment keeps its start; dst is not used)
 };
 
 constexpr int ATT_PAGE_FULL = 0x40000000;   // in ws.att_pages: the page has no empty slot
@@ -251,6 +252,11 @@ kvtrim_status launch_decode_step(kvtrim_ctx*, const CacheViewMut& src, const Ste
                                  const int64_t* budget, float* score, int32_t* kept, uint32_t* thr, const uint16_t* q,
                                  int32_t layer_begin, int32_t layer_end, float scale, float* out, float* lse,
                                  int64_t evict_hint, hipStream_t);
+// The same with stages 3 + 4 inside the cache (four kernels: the row mover is followed by k_cmp_unstage).
+kvtrim_status launch_decode_step_inplace(kvtrim_ctx*, const CacheViewMut& c, const StepArgs& sa, const CacheViewMut& stage,
+                                         const int32_t* now, const int64_t* budget, float* score, int32_t* kept, uint32_t* thr,
+                                         const uint16_t* q, int32_t layer_begin, int32_t layer_end, float scale, float* out,
+                                         float* lse, int64_t evict_hint, hipStream_t);
 kvtrim_status launch_score_select_general(kvtrim_ctx*, const CacheView&, const int32_t* now, const int64_t* budget,
                                           float* score, uint8_t* keep, int32_t* kept, uint32_t* thr, hipStream_t);
 kvtrim_status launch_compact(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const int32_t* kept,

@@ -281,12 +281,14 @@ def compare_cache_contents(hc_gpu, hc_ref):
 
 
 def run_steps_inplace_both(w, steps, budget, room, cache_dict, now0, device="cuda:0", horizon=1, rebalance_at=(),
-                           two_call=False, rebalance_room=None):
+                           two_call=False, rebalance_room=None, one_call=False, hint=0):
     """The decode loop with stages 3 + 4 done inside the cache (kvtrim_compact_attn_inplace): `cache_dict` must leave
     `room` free slots behind every segment (one is used per step).  At the steps listed in `rebalance_at` the GPU
     side runs the out-of-place fused call instead, into a second cache with `room` free slots per segment again
     (`rebalance_room(step)` slots if given: a budget that evicts nothing leaves no space to restore the whole room).
     two_call: stage 3 alone in place (kvtrim_compact_inplace), then kvtrim_decode_attn on the same cache.
+    one_call: the whole step through kvtrim_decode_step_inplace (kvtrim_decode_step at the rebalancing steps) with
+    evict_hint `hint`.
     The oracle runs its four stages; scores, mask, counts, threshold, segment contents and attention are compared."""
     cache_dict = ki.with_horizon(cache_dict, horizon)
     hc = host_cache(w, cache_dict)
@@ -317,13 +319,31 @@ def run_steps_inplace_both(w, steps, budget, room, cache_dict, now0, device="cud
         hc_next = oracle.compact(hc, keep_ref, cap, 1)             # (the oracle packs its segments; one slot for the next token)
         out_ref, lse_ref = oracle.attend(hc_next, bf16_bits(inp["q"]), scale)
         d = {k: v.to(device) for k, v in inp.items()}
-        kv.kvtrim_append(ctx, cur, d["k_new"], d["v_new"], d["log_beta_new"], torch.from_numpy(pos_new).to(device), 1,
-                         log_tail_new=d.get("log_tail_new"))
-        kv.kvtrim_score(ctx, cur, torch.from_numpy(now).to(device), score)
-        kv.kvtrim_select_global(ctx, cur, score, budget_dev, keep, kept, thr)
-        live_gpu = live_mask(device_cache_to_host(w, cur))         # the GPU cache's own layout, after the append
-        score_gpu, keep_gpu = score.cpu().numpy(), keep.cpu().numpy()
-        if step in rebalance_at:
+        if one_call:
+            before = device_cache_to_host(w, cur)
+            before.seg_len = before.seg_len + 1                    # the layout the scores and the mask refer to
+            live_gpu = live_mask(before)
+            args = (d["k_new"], d["v_new"], d["log_beta_new"], torch.from_numpy(pos_new).to(device), 1,
+                    torch.from_numpy(now).to(device), budget_dev, score, keep, kept)
+            if step in rebalance_at:
+                kv.kvtrim_decode_step(ctx, cur, *args, other, room if rebalance_room is None else rebalance_room(step),
+                                      d["q"], 0, w.n_layers, scale, out, lse, thr_key_out=thr,
+                                      log_tail_new=d.get("log_tail_new"), evict_hint=hint)
+                cur, other = other, cur
+            else:
+                kv.kvtrim_decode_step_inplace(ctx, cur, *args, other, d["q"], 0, w.n_layers, scale, out, lse, thr_key_out=thr,
+                                              log_tail_new=d.get("log_tail_new"), evict_hint=hint)
+            score_gpu, keep_gpu = score.cpu().numpy(), keep.cpu().numpy()
+        else:
+            kv.kvtrim_append(ctx, cur, d["k_new"], d["v_new"], d["log_beta_new"], torch.from_numpy(pos_new).to(device), 1,
+                             log_tail_new=d.get("log_tail_new"))
+            kv.kvtrim_score(ctx, cur, torch.from_numpy(now).to(device), score)
+            kv.kvtrim_select_global(ctx, cur, score, budget_dev, keep, kept, thr)
+            live_gpu = live_mask(device_cache_to_host(w, cur))     # the GPU cache's own layout, after the append
+            score_gpu, keep_gpu = score.cpu().numpy(), keep.cpu().numpy()
+        if one_call:
+            pass
+        elif step in rebalance_at:
             kv.kvtrim_compact_attn(ctx, cur, keep, kept, other, room if rebalance_room is None else rebalance_room(step),
                                    d["q"], 0, w.n_layers, scale, out, lse)
             cur, other = other, cur
