@@ -835,7 +835,7 @@ def run_decode(args, brief=False):
     K2 = min(K, 128)
     ROOM = max(2, min(64, K2 // 2))
     cap_room = n_ret + w.nseg * ROOM + 8
-    plain = not (brief or args.paged or args.unfused or args.inplace or args.graph or args.kernel_times or args.pmc_calibration
+    plain = not (brief or args.no_inplace_leg or args.paged or args.unfused or args.inplace or args.graph or args.kernel_times or args.pmc_calibration
                  or args.separate_score_select or args.separate_calls)
     if plain and cap_room <= r.cap:
         s0 = n_steps
@@ -958,6 +958,9 @@ def main():
     ap.add_argument("--chunk", type=int, default=0, metavar="N_TOK",
                     help="time the chunked-prefill step of the multi-turn workload instead of decode steps: N_TOK new "
                          "tokens per segment, then rescore, select, compact (the paper-shaped chunk is 4096)")
+    ap.add_argument("--no-inplace-leg", action="store_true",
+                    help="do not time the in-place variant behind the metric's steps (for profiles: its launches of the scoring and "
+                         "merge kernels would mix into the per-kernel means)")
     ap.add_argument("--inplace", type=int, default=0, metavar="ROOM",
                     help="compact inside the cache (kvtrim_compact_attn_inplace: rows move only behind an eviction) with ROOM "
                          "free slots behind every segment; every ROOM-th step is an out-of-place step that evens the room out")
