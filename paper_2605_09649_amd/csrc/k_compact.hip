@@ -387,79 +387,6 @@ __global__ __launch_bounds__(CMP_THREADS) void k_cmp_copy(CacheView src, const u
     }
 }
 
-// The row mover for a SPARSE selection (a destination so much smaller than the source that few rows can survive:
-// the first eviction after a long prefill keeps one entry in sixteen).  One WAVEFRONT per chunk instead of one block:
-// with a handful of survivors per chunk, seven of k_cmp_copy's eight wavefronts only wait at its barriers, and the
-// chunks in flight - each a chain of dependent loads (descriptor, mask, rows) - are too few to fill the memory
-// system.  Here every resident wavefront has a chunk of its own and there is no block-level barrier: the survivor
-// list of a chunk is written and read by one wavefront, whose LDS operations complete in order.
-constexpr int GAT_WAVES = 4;
-
-template <int D>
-__global__ __launch_bounds__(GAT_WAVES * 64) void k_cmp_gather(CacheView src, const uint8_t* __restrict__ keep,
-                                                               CacheViewMut dst, Shape sh, Workspace ws) {
-    constexpr int VPR = D / 8;                    // 16-byte vectors per row
-    constexpr int RPI = 64 / VPR;                 // rows moved by one wavefront instruction
-    constexpr int BATCH = CMP_WAVE_ROWS / RPI;    // instructions per batch: 4 (D=128) or 2 (D=64)
-    __shared__ uint8_t s_list[GAT_WAVES][CMP_CHUNK];
-    const int lane = lane_id(), wave = threadIdx.x >> 6;
-    if (__hip_atomic_load(ws.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
-    const int total = ws.cmp_chunk_prefix[sh.nseg];
-    const int ch = blockIdx.x * GAT_WAVES + wave;
-    if (ch >= total) return;                                      // (whole wavefronts leave; nobody waits for them)
-    const ChunkDesc d = ws.cmp_desc[ch];
-    const int64_t sbase = d.first;
-    const int64_t dbase = ws.cmp_chunk_dst[ch] & ~CMP_DST_FULL;
-    static_assert(CMP_CHUNK == 128, "two entries of the chunk per lane");
-    const bool f0 = lane < d.n && keep[sbase + lane] != 0;
-    const bool f1 = lane + 64 < d.n && keep[sbase + 64 + lane] != 0;
-    const uint64_t m0 = __ballot(f0), m1 = __ballot(f1);
-    const int n0 = __popcll(m0), cnt = n0 + __popcll(m1);
-    if (cnt == 0) return;
-    uint8_t* list = s_list[wave];
-    if (f0) {
-        const int r = mbcnt(m0);
-        list[r] = (uint8_t)lane;
-        dst.log_beta[dbase + r] = src.log_beta[sbase + lane];
-        if (src.log_tail) dst.log_tail[dbase + r] = src.log_tail[sbase + lane];
-        dst.pos[dbase + r] = src.pos[sbase + lane];
-    }
-    if (f1) {
-        const int r = n0 + mbcnt(m1);
-        list[r] = (uint8_t)(lane + 64);
-        dst.log_beta[dbase + r] = src.log_beta[sbase + 64 + lane];
-        if (src.log_tail) dst.log_tail[dbase + r] = src.log_tail[sbase + 64 + lane];
-        dst.pos[dbase + r] = src.pos[sbase + 64 + lane];
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");        // (orders the compiler; the hardware keeps a wavefront's LDS operations in order)
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    const uint4* sk = reinterpret_cast<const uint4*>(src.k);
-    const uint4* sv = reinterpret_cast<const uint4*>(src.v);
-    uint4* dk = reinterpret_cast<uint4*>(dst.k);
-    uint4* dv = reinterpret_cast<uint4*>(dst.v);
-    const int sub = lane / VPR, col = lane % VPR;
-    for (int r0 = 0; r0 < cnt; r0 += CMP_WAVE_ROWS) {             // (one pass for up to 16 survivors)
-        uint4 kk[BATCH], vv[BATCH];
-#pragma unroll
-        for (int u = 0; u < BATCH; ++u) {
-            const int r = min(r0 + u * RPI + sub, cnt - 1);       // clamped: loads stay on live rows
-            const int64_t se = (sbase + list[r]) * VPR + col;
-            kk[u] = ld16_nt(sk + se);
-            vv[u] = ld16_nt(sv + se);
-        }
-#pragma unroll
-        for (int u = 0; u < BATCH; ++u) {
-            const int r = r0 + u * RPI + sub;
-            if (r < cnt) {
-                const int64_t de = (dbase + r) * VPR + col;
-                st16_nt(dk + de, kk[u]);
-                st16_nt(dv + de, vv[u]);
-            }
-        }
-    }
-}
-
 void launch_cmp_scan_aligned(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const int32_t* kept,
                              const CacheViewMut& dst, int32_t reserve, int32_t align, hipStream_t st, bool gat) {
     ProfScope prof(ctx, K_CMP_SCAN, st);
@@ -498,11 +425,12 @@ void launch_cmp_scan(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep,
 
 kvtrim_status launch_compact(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const int32_t* kept,
                              const CacheViewMut& dst, int32_t reserve, hipStream_t st) {
-    launch_cmp_scan(ctx, src, keep, kept, dst, reserve, st);
+    launch_cmp_scan_aligned(ctx, src, keep, kept, dst, reserve, 1, st, gather_fits(ctx, src.cap, dst.cap));
     return launch_cmp_copy(ctx, src, keep, dst, st);
 }
 
-// The row mover alone (the tables of k_cmp_scan must be in the workspace).
+// The row mover alone (the tables of k_cmp_scan must be in the workspace - with gat = gather_fits(...), which decides
+// here which mover runs).
 kvtrim_status launch_cmp_copy(kvtrim_ctx* ctx, const CacheView& src, const uint8_t* keep, const CacheViewMut& dst,
                               hipStream_t st) {
     const Shape& sh = ctx->shape;
@@ -511,15 +439,9 @@ kvtrim_status launch_cmp_copy(kvtrim_ctx* ctx, const CacheView& src, const uint8
     if (max_chunks > 0) {
         ProfScope prof(ctx, K_CMP_COPY, st);
         const dim3 grid((unsigned)max_chunks), block(CMP_THREADS);
-        // A destination under a quarter of the source cannot take more than one source entry in four: few survivors
-        // per chunk, the wavefront-per-chunk mover (33.5 M entries -> 2.1 M: 848 -> 532 us).
-        if (dst.cap < src.cap / 4) {
-            const dim3 ggrid((unsigned)((max_chunks + GAT_WAVES - 1) / GAT_WAVES)), gblock(GAT_WAVES * 64);
-            if (sh.head_dim == 128)
-                hipLaunchKernelGGL(k_cmp_gather<128>, ggrid, gblock, 0, st, src, keep, dst, sh, ws);
-            else
-                hipLaunchKernelGGL(k_cmp_gather<64>, ggrid, gblock, 0, st, src, keep, dst, sh, ws);
-        } else if (sh.head_dim == 128)
+        if (gather_fits(ctx, src.cap, dst.cap))                   // few survivors per chunk: a block per chunk of the destination
+            return launch_gather_rows(ctx, src, dst, st);
+        if (sh.head_dim == 128)
             hipLaunchKernelGGL((k_cmp_copy<128, false>), grid, block, 0, st, src, keep, dst, sh, ws, nullptr, nullptr, 0, nullptr);
         else
             hipLaunchKernelGGL((k_cmp_copy<64, false>), grid, block, 0, st, src, keep, dst, sh, ws, nullptr, nullptr, 0, nullptr);

@@ -451,6 +451,19 @@ static bool dispatch_gather(int G, dim3 grid, hipStream_t st, const CacheView& s
     }
 }
 
+// Stage 3 alone for a sparse selection: the gathering instance with no layer to attend (it then reads no query and
+// writes no partial result).
+kvtrim_status launch_gather_rows(kvtrim_ctx* ctx, const CacheView& src, const CacheViewMut& dst, hipStream_t st) {
+    const Shape& sh = ctx->shape;
+    const dim3 grid((unsigned)(dst.cap / CMP_CHUNK + sh.nseg));
+    if (sh.head_dim == 128)
+        hipLaunchKernelGGL((k_cmp_attn<128, 1, false, false, true>), grid, dim3(FUS_THREADS), 0, st, src, nullptr, dst, dst, nullptr, sh, ctx->ws, 0.f, 0, 0);
+    else
+        hipLaunchKernelGGL((k_cmp_attn<64, 1, false, false, true>), grid, dim3(FUS_THREADS), 0, st, src, nullptr, dst, dst, nullptr, sh, ctx->ws, 0.f, 0, 0);
+    KVTRIM_HIP(ctx, hipGetLastError());
+    return KVTRIM_OK;
+}
+
 // After k_cmp_attn<.., INPLACE>: the survivors of a chunk whose place lies before the chunk's own range (as many
 // as were evicted before the chunk in its segment, at most all of its survivors) wait in `stage` at their final
 // index; one wavefront per chunk puts them there (in a decode step most chunks have nothing parked and their
@@ -620,8 +633,7 @@ kvtrim_status launch_compact_attn(kvtrim_ctx* ctx, const CacheView& src, const u
     // take more than one source entry in four.
     const bool sparse = evict_hint > 0 ? false : dst.cap < src.cap / 4;
     const int64_t dst_chunks = dst.cap / CMP_CHUNK + sh.nseg;    // upper bound on the destination's chunks
-    if (sparse && dst_chunks <= ws.max_att_chunks && dst_chunks * CMP_CHUNK <= ws.gat_slots &&
-        max_chunks <= ws.max_cmp_chunks) {
+    if (sparse && gather_fits(ctx, src.cap, dst.cap)) {
         // Few survivors per source chunk: the fused kernel's gathering instance, a block per chunk of the destination
         // (a block per source chunk would write one partial result per 128 source entries for a handful of survivors
         // each).  The compaction scan lists the destination's chunks and the source row of each of their rows.

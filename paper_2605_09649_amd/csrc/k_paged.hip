@@ -970,7 +970,7 @@ kvtrim_status kvtrim_paged_build(kvtrim_ctx* ctx, const kvtrim_cache* src, const
     dv.seg_len = ctx->ws.pg_seg_len;
     dv.cap = (int64_t)dst->n_pages * P;
     dv.log_tail = dst->log_tail;
-    launch_cmp_scan_aligned(ctx, sv, keep, kept, dv, 0, P, st);
+    launch_cmp_scan_aligned(ctx, sv, keep, kept, dv, 0, P, st, gather_fits(ctx, sv.cap, dv.cap));
     kvtrim_status rc = launch_cmp_copy(ctx, sv, keep, dv, st);
     if (rc != KVTRIM_OK) return rc;
     {

@@ -273,6 +273,17 @@ kvtrim_status launch_attn_paged(kvtrim_ctx*, const CacheView& pool, const int32_
 // row of every destination row (ws.gat_src) - what the gathering instance of the fused kernel reads.
 void launch_cmp_scan_aligned(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const int32_t* kept,
                              const CacheViewMut& dst, int32_t reserve, int32_t align, hipStream_t, bool gat = false);
+// A selection that keeps few entries of every chunk (a destination under a quarter of the source cannot take more than
+// one source entry in four) whose tables fit the workspace: the compaction scan then also lists the destination's chunks
+// and the source row of every destination row, and the rows are moved a block per chunk of the DESTINATION.
+inline bool gather_fits(const kvtrim_ctx* ctx, int64_t src_cap, int64_t dst_cap) {
+    const int64_t dst_chunks = dst_cap / kvtrim::CMP_CHUNK + ctx->shape.nseg;
+    return dst_cap < src_cap / 4 && dst_chunks <= ctx->ws.max_att_chunks && dst_chunks * kvtrim::CMP_CHUNK <= ctx->ws.gat_slots &&
+           src_cap / kvtrim::CMP_CHUNK + ctx->shape.nseg <= ctx->ws.max_cmp_chunks;
+}
+// The gathering instance of the fused kernel without the attention (the tables of a compaction scan with gat = true
+// must be in the workspace).
+kvtrim_status launch_gather_rows(kvtrim_ctx*, const CacheView& src, const CacheViewMut& dst, hipStream_t);
 kvtrim_status launch_cmp_copy(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const CacheViewMut& dst,
                               hipStream_t);
 kvtrim_status launch_occupancy(kvtrim_ctx*, const CacheView&, const int32_t* now, double* occ, hipStream_t);

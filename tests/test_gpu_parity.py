@@ -252,10 +252,10 @@ def test_fused_call_with_a_layer_range_and_sparse_mask(roomy, G, D):
 
 
 @pytest.mark.parametrize("D,horizon", [(128, 1), (64, 1), (128, 2)])
-def test_sparse_selection_takes_the_wavefront_per_chunk_mover(D, horizon):
-    # a destination under a quarter of the source: the row mover works a wavefront per 128-entry chunk.  One entry in
-    # sixteen survives on average; some chunks keep nothing, some keep every entry (more than one batch of 16 rows per
-    # wavefront), segments end in ragged chunks, one segment is empty.
+def test_sparse_selection_in_stage_three_alone_gathers_by_destination_chunk(D, horizon):
+    # a destination under a quarter of the source: the row mover works a block per 128-row chunk of the DESTINATION
+    # (the fused kernel's gathering instance with no layer to attend).  One entry in sixteen survives on average; some
+    # source chunks keep nothing, some keep every entry, segments end in ragged chunks, one segment is empty.
     w = wl(2, 2, 3, 2, D)
     rng = np.random.default_rng(77 + D + horizon)
     seg_len = rng.integers(1, 6000, w.nseg)
