@@ -50,6 +50,19 @@ def test_steady_state_in_place_whole(name):
     check(res)
 
 
+@pytest.mark.parametrize("name", ["llama", "vlm"])
+def test_steady_state_in_place_whole_in_one_call(name):
+    # the same through kvtrim_decode_step (the first eviction, given a decode step's hint: there is no bound yet and far
+    # more goes than the hint says, so the scoring kernel's single-block select runs and hands over a mask and a table
+    # instead of lists) and kvtrim_decode_step_inplace (three steps of four kernels)
+    w = ki.workload(name)
+    pre = {k: (v.cpu() if torch.is_tensor(v) else v) for k, v in ki.prefill_cache(w, reserve=4, device=DEV).items()}
+    res = run_steps_inplace_both(w, 4, w.budget, 4, pre, [t - 1 for t in w.prefill], device=DEV, rebalance_at=(0,), one_call=True,
+                                 hint=w.n_layers * w.n_kv_heads)
+    assert [r["in_place"] for r in res] == [False, True, True, True]
+    check(res)
+
+
 def test_vlm_two_sequences_whole():
     w = ki.workload("vlm")
     pre = {k: (v.cpu() if torch.is_tensor(v) else v) for k, v in ki.prefill_cache(w, device=DEV).items()}
