@@ -85,6 +85,11 @@ class Loop:
         else:
             dst = self.spare[self.flip]
             hint = w.n_layers * w.n_kv_heads                      # evictions per sequence and step once at the budget
+            if self.calls == "decode_step_inplace":               # the whole step in one call, inside the cache
+                kv.kvtrim_decode_step_inplace(ctx, self.cur, i["k_new"], i["v_new"], i["log_beta_new"], self.pos[slot], 1,
+                                              self.now[slot], self.budget, self.score, self.keep, self.kept, dst, i["q"], 0,
+                                              w.n_layers, self.scale, self.out[slot], thr_key_out=self.thr, evict_hint=hint)
+                return
             if self.calls == "decode_step":                       # the whole step in one call
                 kv.kvtrim_decode_step(ctx, self.cur, i["k_new"], i["v_new"], i["log_beta_new"], self.pos[slot], 1, self.now[slot],
                                       self.budget, self.score, self.keep, self.kept, dst, 1, i["q"], 0, w.n_layers, self.scale,
@@ -133,11 +138,11 @@ def same(a, b):
                               b[k].view(np.uint8) if b[k].dtype.kind == "f" else b[k]) for k in a) and a.keys() == b.keys()
 
 
-@pytest.mark.parametrize("paged", [False, True, "inplace", "score_select", "decode_step", "paged_decode_step"])
+@pytest.mark.parametrize("paged", [False, True, "inplace", "score_select", "decode_step", "decode_step_inplace", "paged_decode_step"])
 def test_two_captured_steps_replayed_three_times_match_the_eager_loop(paged):
     w = ki.workload("tiny", prefill=900)
-    calls = paged if paged in ("score_select", "decode_step", "paged_decode_step") else "four"
-    inplace, paged = paged == "inplace", paged is True or paged == "paged_decode_step"
+    calls = paged if paged in ("score_select", "decode_step", "decode_step_inplace", "paged_decode_step") else "four"
+    inplace, paged = paged in ("inplace", "decode_step_inplace"), paged is True or paged == "paged_decode_step"
     eager, graphed = Loop(w, paged, inplace, calls), Loop(w, paged, inplace, calls)
     for loop in (eager, graphed):
         loop.first_step()
