@@ -53,7 +53,7 @@ def test_lookahead_horizon(horizon):
 
 
 @pytest.mark.parametrize("S,L,H,G,D", [(1, 2, 2, 1, 128), (2, 2, 1, 5, 128), (3, 1, 2, 3, 64), (1, 2, 1, 4, 128), (1, 1, 3, 4, 64),
-                                       (1, 1, 2, 7, 128)])
+                                       (1, 1, 2, 7, 128), (1, 1, 2, 8, 128), (2, 1, 1, 6, 128), (1, 2, 1, 8, 64), (1, 1, 2, 5, 64)])
 def test_ragged_segments_spanning_several_blocks(S, L, H, G, D):
     w = wl(S, L, H, G, D)
     rng = np.random.default_rng(S * 1000 + G * 10 + D)

@@ -107,6 +107,45 @@ def test_many_segments_and_sequences():
     check(run_steps_inplace_both(w, 3, [n - 300 for n in per_seq], 3, c, now.numpy(), device=DEV, one_call=True, hint=per))
 
 
+@pytest.mark.parametrize("G", [4, 8])
+def test_layer_range(G):
+    # a layer range attends only its layers (the other rows of `out` stay as they were) while every segment is
+    # compacted; the attended rows, the mask, the counts and the cache equal those of a full-range call on a copy of
+    # the cache, in the four-kernel form (second step: the bound is there) as in the separate calls (first step)
+    from harness import compare_cache_contents, device_cache_to_host
+    w = wl(1, 3, 2, G, 128)
+    seg_len = [400, 130, 700, 5, 256, 300]
+    c, now = ki.ragged_cache(w, seg_len, reserve=3, salt=11)
+    cap = c["cap"]
+    spare = kv.Cache.empty(w.nseg, 128, cap, DEV)
+    budget = torch.tensor([sum(seg_len) - 40], dtype=torch.int64, device=DEV)
+    res = []
+    for rng in ((0, 3), (1, 2)):
+        ctx = kv.Context(1, 3, 2, 2 * G, 128, cap)
+        cache = kv.Cache.from_dict({k: (v.clone() if torch.is_tensor(v) else v) for k, v in c.items()}, DEV)
+        score, keep = torch.zeros(cap, dtype=torch.float32, device=DEV), torch.zeros(cap, dtype=torch.uint8, device=DEV)
+        kept = torch.zeros(w.nseg, dtype=torch.int32, device=DEV)
+        outs = []
+        for step in range(3):
+            inp = {k: v.to(DEV) for k, v in ki.decode_inputs(w, step).items()}
+            t = int(now[0]) + 1 + step
+            out = torch.full((1, 3, 2 * G, 128), 7.0, dtype=torch.float32, device=DEV)
+            kv.kvtrim_decode_step_inplace(ctx, cache, inp["k_new"], inp["v_new"], inp["log_beta_new"],
+                                          torch.full((w.nseg,), t, dtype=torch.int32, device=DEV), 1,
+                                          torch.tensor([t], dtype=torch.int32, device=DEV), budget, score, keep, kept, spare,
+                                          inp["q"], rng[0], rng[1], 0.0884, out, evict_hint=w.nseg)
+            assert kv.kvtrim_poll_error(ctx) == 0
+            outs.append(out.cpu())
+        assert kv.kvtrim_select_path_counts(ctx)[0] >= 1          # (the candidate list carried a step: the four kernels ran)
+        res.append((outs, keep.cpu(), kept.cpu(), device_cache_to_host(w, cache)))
+    (full, keep_a, kept_a, cache_a), (part, keep_b, kept_b, cache_b) = res
+    for step in range(3):
+        assert torch.equal(part[step][:, 1], full[step][:, 1])
+        assert bool((part[step][:, 0] == 7.0).all()) and bool((part[step][:, 2] == 7.0).all())
+    assert torch.equal(keep_a, keep_b) and torch.equal(kept_a, kept_b)
+    assert compare_cache_contents(cache_b, cache_a)
+
+
 def test_no_room_for_the_new_token_is_reported():
     w = wl(1, 1, 2, 2, 64)
     seg_len = [100, 50]
