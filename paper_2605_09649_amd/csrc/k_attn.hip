@@ -23,6 +23,8 @@ typedef __attribute__((ext_vector_type(4))) float float4v;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) short short4v;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) unsigned v4u;
+typedef __attribute__((ext_vector_type(2))) unsigned v2u;
 
 __global__ __launch_bounds__(1024) void k_att_plan(CacheView c, Shape sh, Workspace ws, int chunk,
                                                    int layer_begin, int layer_end, int64_t max_chunks) {
@@ -45,6 +47,10 @@ struct Frag<128> {
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
     }
     static __device__ __forceinline__ vec zero() { return make_uint4(0, 0, 0, 0); }
+    static __device__ __forceinline__ vec ld(const vec* p) {     // K and V rows are read once per call: a streaming load
+        const v4u t = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(p));
+        return make_uint4(t.x, t.y, t.z, t.w);
+    }
     static __device__ __forceinline__ unsigned word(vec x, int w) { return w == 0 ? x.x : (w == 1 ? x.y : (w == 2 ? x.z : x.w)); }
 };
 template <>
@@ -55,6 +61,10 @@ struct Frag<64> {
         return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(short4v, a), __builtin_bit_cast(short4v, b), c, 0, 0, 0);
     }
     static __device__ __forceinline__ vec zero() { return make_uint2(0, 0); }
+    static __device__ __forceinline__ vec ld(const vec* p) {
+        const v2u t = __builtin_nontemporal_load(reinterpret_cast<const v2u*>(p));
+        return make_uint2(t.x, t.y);
+    }
     static __device__ __forceinline__ unsigned word(vec x, int w) { return w == 0 ? x.x : x.y; }
 };
 
@@ -134,10 +144,15 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
         const int64_t krow = rbase + min(r0 + c16, last);
         vec kf[4], vf[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) kf[j] = kp[krow * VPR + 4 * j + b4];
+        for (int j = 0; j < 4; ++j) kf[j] = F::ld(kp + krow * VPR + 4 * j + b4);
         // V coalesced: lane -> row r0 + 4*b4 + i, vector c16
 #pragma unroll
-        for (int i = 0; i < 4; ++i) vf[i] = vp[(rbase + min(r0 + 4 * b4 + i, last)) * VPR + c16];
+        for (int i = 0; i < 4; ++i) vf[i] = F::ld(vp + (rbase + min(r0 + 4 * b4 + i, last)) * VPR + c16);
+        int ps[4] = {0, 0, 0, 0};                                 // positions of the lane's rows, asked for with the rows
+        if (PAGED && holes) {                                     // (uniform over the wavefront)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) ps[i] = c.pos[rbase + min(r0 + 4 * b4 + i, last)];
+        }
 
         float4v acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -152,8 +167,8 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
             float zi = acc[i] * scale_log2;
             if (SOFT) zi = fmaf((float)(t_now - c.pos[e]) * c.log_beta[e], 1.4426950408889634f, zi);
             bool valid = row < row_end;
-            if (PAGED && holes) {                                 // (uniform over the wavefront)
-                valid = valid && c.pos[e] >= 0;
+            if (PAGED && holes) {
+                valid = valid && ps[i] >= 0;
                 if (!valid) vf[i] = F::zero();
             }
             z[i] = valid ? zi : -INFINITY;
