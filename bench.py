@@ -412,7 +412,7 @@ class Runner:
             return
         cur = self.cur
         if a.inplace and not (a.unfused or a.separate_score_select or a.separate_calls) and s > 0:
-            # the whole step in one call, inside the cache (four kernels) or - every ROOM-th step - out of place
+            # the whole step in one call, inside the cache (three kernels) or - every ROOM-th step - out of place
             new = (inp["k_new"], inp["v_new"], inp["log_beta_new"], self.pos_news[s], 1, self.nows[s], self.budget, self.score,
                    self.keep, self.kept)
             dst = self.spare[self.flip]
@@ -691,7 +691,7 @@ def run_decode(args, brief=False):
                f"{args.inplace}th step an out-of-place compact_attn)" if args.inplace else
                "compact_attn (stages 3+4 fused)")))
     if args.inplace and not (args.paged or args.unfused or args.separate_score_select or args.separate_calls):
-        calls = (f"decode_step_inplace (append, stages 1-4 in one call, stages 3+4 inside the cache: four kernels per decode step; "
+        calls = (f"decode_step_inplace (append, stages 1-4 in one call, stages 3+4 inside the cache: three kernels per decode step; "
                  f"{args.inplace} free slots per segment, every {args.inplace}th step an out-of-place decode_step)")
     result = {
         "metric": metric_name(w),
@@ -895,7 +895,7 @@ def run_decode(args, brief=False):
         result["in_place_variant"] = {
             "ms_per_step": ms_room, "value": 1e3 / ms_room, "unit": "steps/s", "steps": K2 - 1, "room": ROOM,
             "out_of_place_steps_in_timed_region": n_oop, "parity_on_last_step": parity_ip,
-            "what": "kvtrim_decode_step_inplace (four kernels per decode step): a row moves only if an entry before it in its "
+            "what": "kvtrim_decode_step_inplace (three kernels per decode step): a row moves only if an entry before it in its "
                     f"segment was evicted; every {ROOM}th step is an out-of-place kvtrim_decode_step that evens the free slots out"}
         del big, extra
     del r

@@ -414,8 +414,10 @@ kvtrim_status kvtrim_paged_score_select(kvtrim_ctx *ctx, const kvtrim_paged_cach
  *     kvtrim_paged_append(one token per segment) -> kvtrim_paged_score_select(now, budget, evict_hint)
  *     -> kvtrim_paged_evict(keep_out) -> kvtrim_paged_attn(q)
  * leave there (arguments as in those four calls; one row per segment in the new-token arrays).  With a small
- * evict_hint the mask kernel of the decode-step selection applies the eviction as it writes the mask, which saves
- * the pass of kvtrim_paged_evict over all pages: seven kernels per step.  Any other hint runs the four calls. */
+ * evict_hint the mask kernel of the decode-step selection applies the eviction as it writes the mask (which saves
+ * the pass of kvtrim_paged_evict over all pages), its scoring kernel also builds the attention's chunk table, and
+ * the attention's merge kernel takes the emptied pages out of the block tables: five kernels per step.  Any other
+ * hint runs the four calls. */
 kvtrim_status kvtrim_paged_decode_step(kvtrim_ctx *ctx, kvtrim_paged_cache *c, const void *k_new, const void *v_new,
                                        const float *log_beta_new, const float *log_tail_new, const int32_t *pos_new,
                                        const int32_t *now, const int64_t *budget, float *score_out, uint8_t *keep_out,

@@ -13,7 +13,7 @@
 // A wavefront keeps one online-softmax stream per query head (the maximum over the tile's 16
 // rows); at the end of the chunk the four wavefronts are merged through LDS, and the chunks of
 // a segment by k_att_combine.  Logits are kept in base-2 units.
-#include "kvtrim_device.h"
+#include "kvtrim_paged_device.h"
 
 namespace kvtrim {
 
@@ -118,25 +118,22 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
     const vec* vp = reinterpret_cast<const vec*>(c.v);
     constexpr int VPR = D / E;                                    // vectors per row = 16
 
-    // PAGED: the (at most four) pages of the run come from the plan kernel's table beside the descriptors, so no
+    // PAGED: the (at most four) pages of the run come from the plan's table beside the descriptors, so no
     // load of the loop waits for a look-up in the block table
-    int pg0 = 0, pg1 = 0, pg2 = 0, pg3 = 0, full = 0;             // full: bit i = page i of the run has no empty slot
+    int pg0 = 0, pg1 = 0, pg2 = 0, pg3 = 0;
     if (PAGED) {
         const int np = row_end >> 7, hi = (int)(c.cap >> 7) - 1;
-        pg0 = min(max(pgs.x & ~ATT_PAGE_FULL, 0), hi);
-        pg1 = np > 1 ? min(max(pgs.y & ~ATT_PAGE_FULL, 0), hi) : 0;
-        pg2 = np > 2 ? min(max(pgs.z & ~ATT_PAGE_FULL, 0), hi) : 0;
-        pg3 = np > 3 ? min(max(pgs.w & ~ATT_PAGE_FULL, 0), hi) : 0;
-        full = (pgs.x >= ATT_PAGE_FULL) | ((pgs.y >= ATT_PAGE_FULL) << 1) | ((pgs.z >= ATT_PAGE_FULL) << 2) | ((pgs.w >= ATT_PAGE_FULL) << 3);
+        pg0 = min(max(pgs.x, 0), hi);
+        pg1 = np > 1 ? min(max(pgs.y, 0), hi) : 0;
+        pg2 = np > 2 ? min(max(pgs.z, 0), hi) : 0;
+        pg3 = np > 3 ? min(max(pgs.w, 0), hi) : 0;
     }
 
     for (int r0 = off + wave * 16; r0 < row_end; r0 += 64) {
         const int last = row_end - 1;
         int64_t rbase = base;                                     // entry of row 0 in this 16-row group's numbering
-        bool holes = PAGED;                                       // the group's page may have empty slots: look at the positions
         if (PAGED) {                                              // 16 | page size: the group lies in one page
             const int pi = r0 >> 7;
-            holes = !((full >> pi) & 1);
             const int pg = pi == 0 ? pg0 : (pi == 1 ? pg1 : (pi == 2 ? pg2 : pg3));
             rbase = (int64_t)pg * KVTRIM_PAGE_SIZE - (r0 & ~(KVTRIM_PAGE_SIZE - 1));
         }
@@ -148,8 +145,8 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
         // V coalesced: lane -> row r0 + 4*b4 + i, vector c16
 #pragma unroll
         for (int i = 0; i < 4; ++i) vf[i] = F::ld(vp + (rbase + min(r0 + 4 * b4 + i, last)) * VPR + c16);
-        int ps[4] = {0, 0, 0, 0};                                 // positions of the lane's rows, asked for with the rows
-        if (PAGED && holes) {                                     // (uniform over the wavefront)
+        int ps[4] = {0, 0, 0, 0};                                 // PAGED: the positions of the lane's slots, asked for with the rows
+        if (PAGED) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) ps[i] = c.pos[rbase + min(r0 + 4 * b4 + i, last)];
         }
@@ -167,7 +164,7 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
             float zi = acc[i] * scale_log2;
             if (SOFT) zi = fmaf((float)(t_now - c.pos[e]) * c.log_beta[e], 1.4426950408889634f, zi);
             bool valid = row < row_end;
-            if (PAGED && holes) {
+            if (PAGED) {                                          // an empty slot takes no part
                 valid = valid && ps[i] >= 0;
                 if (!valid) vf[i] = F::zero();
             }
@@ -264,16 +261,36 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
 // the tile with loads that do not depend on each other, so all of them are in flight at once.
 constexpr int COMB_TILE = 128;
 constexpr int COMB_THREADS = 512;
-template <int D>
+// Housekeeping that nothing in this launch reads rides behind the merging blocks of the grid, so that it needs no
+// launch of its own:
+//   EXTRA_TIDY (the paged decode step in one call): one block per segment takes the pages emptied by the step's
+//              eviction out of the segment's block table;
+//   EXTRA_UNSTAGE (the in-place compaction with attention): one wavefront per chunk of the row mover's table puts the
+//              rows that the mover parked into their places.
+constexpr int EXTRA_NONE = 0, EXTRA_TIDY = 1, EXTRA_UNSTAGE = 2;
+struct CombineExtra {
+    PagedView tidy;
+    CacheViewMut c, stage;
+    const int32_t* kept;
+};
+
+template <int D, int EXTRA>
 __global__ __launch_bounds__(COMB_THREADS) void k_att_combine(Shape sh, Workspace ws,
                                                               const int32_t* __restrict__ chunk_prefix,
                                                               int layer_begin, int layer_end,
-                                                              float* __restrict__ out, float* __restrict__ lse) {
+                                                              float* __restrict__ out, float* __restrict__ lse,
+                                                              CombineExtra ex) {
     __shared__ float s_m[COMB_TILE][8], s_w[COMB_TILE][8], s_l[COMB_TILE][8];
     __shared__ float s_M[8], s_a[8], s_L[8];
     const int G = sh.group;
     const int nl = layer_end - layer_begin;
     const int per = nl * sh.n_kv_heads;
+    if (EXTRA != EXTRA_NONE && (int)blockIdx.x >= sh.n_seq * per) {
+        const int xb = (int)blockIdx.x - sh.n_seq * per;
+        if (EXTRA == EXTRA_TIDY) tidy_segment<COMB_THREADS>(ex.tidy, xb, ws.err);
+        if (EXTRA == EXTRA_UNSTAGE) unstage_chunk<D>(ex.c, ex.stage, ex.kept, sh, ws, xb * (COMB_THREADS / 64) + (int)(threadIdx.x >> 6));
+        return;
+    }
     const int seq = blockIdx.x / per, r = blockIdx.x % per;
     const int layer = layer_begin + r / sh.n_kv_heads, head = r % sh.n_kv_heads;
     const int seg = (seq * sh.n_layers + layer) * sh.n_kv_heads + head;
@@ -405,7 +422,7 @@ kvtrim_status launch_attn(kvtrim_ctx* ctx, const CacheView& c, const uint16_t* q
 // per-segment merge.
 kvtrim_status launch_attn_paged(kvtrim_ctx* ctx, const CacheView& pool, const int32_t* block_table, const uint16_t* q,
                                 int max_chunks, int32_t layer_begin, int32_t layer_end, float scale, float* out,
-                                float* lse, hipStream_t st) {
+                                float* lse, hipStream_t st, const PagedView* tidy) {
     const Shape& sh = ctx->shape;
     Workspace ws = ctx->ws;
     ws.pg_block_table = block_table;
@@ -418,7 +435,18 @@ kvtrim_status launch_attn_paged(kvtrim_ctx* ctx, const CacheView& pool, const in
                  : dispatch_partial<64>(sh.group, pool, q, sh, ws, KVTRIM_PAGE_SIZE, scale_log2, nullptr, true, (unsigned)max_chunks, st);
     }
     if (!ok) return KVTRIM_EINVAL;
-    return launch_combine(ctx, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, st);
+    if (!tidy) return launch_combine(ctx, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, st);
+    // the merge, and in the same launch one block per segment that tidies its block table
+    CombineExtra ex{};
+    ex.tidy = *tidy;
+    const unsigned nblk = (unsigned)(sh.n_seq * (layer_end - layer_begin) * sh.n_kv_heads + sh.nseg);
+    ProfScope prof(ctx, K_ATT_COMBINE, st);
+    if (sh.head_dim == 128)
+        hipLaunchKernelGGL((k_att_combine<128, EXTRA_TIDY>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, ex);
+    else
+        hipLaunchKernelGGL((k_att_combine<64, EXTRA_TIDY>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, ex);
+    KVTRIM_HIP(ctx, hipGetLastError());
+    return KVTRIM_OK;
 }
 
 // Merges the per-chunk partial results in ws.att_partial; chunk_prefix[g] .. chunk_prefix[g+1]
@@ -430,9 +458,31 @@ kvtrim_status launch_combine(kvtrim_ctx* ctx, const int32_t* chunk_prefix, int32
     const unsigned nblk = (unsigned)(sh.n_seq * (layer_end - layer_begin) * sh.n_kv_heads);
     ProfScope prof(ctx, K_ATT_COMBINE, st);
     if (sh.head_dim == 128)
-        hipLaunchKernelGGL(k_att_combine<128>, dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse);
+        hipLaunchKernelGGL((k_att_combine<128, EXTRA_NONE>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse, CombineExtra{});
     else
-        hipLaunchKernelGGL(k_att_combine<64>, dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse);
+        hipLaunchKernelGGL((k_att_combine<64, EXTRA_NONE>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse, CombineExtra{});
+    KVTRIM_HIP(ctx, hipGetLastError());
+    return KVTRIM_OK;
+}
+
+// The merge after the in-place row mover: the launch also puts the rows that the mover parked in `stage` into their
+// places (one wavefront per chunk of the mover's table, max_chunks of them) and commits the segments' new lengths.
+kvtrim_status launch_combine_unstage(kvtrim_ctx* ctx, const int32_t* chunk_prefix, int32_t layer_begin, int32_t layer_end,
+                                     float* out, float* lse, const CacheViewMut& c, const CacheViewMut& stage,
+                                     const int32_t* kept, int64_t max_chunks, hipStream_t st) {
+    const Shape& sh = ctx->shape;
+    const Workspace& ws = ctx->ws;
+    CombineExtra ex{};
+    ex.c = c;
+    ex.stage = stage;
+    ex.kept = kept;
+    const int64_t per_block = COMB_THREADS / 64;
+    const unsigned nblk = (unsigned)(sh.n_seq * (layer_end - layer_begin) * sh.n_kv_heads + (max_chunks + per_block - 1) / per_block);
+    ProfScope prof(ctx, K_ATT_COMBINE, st);
+    if (sh.head_dim == 128)
+        hipLaunchKernelGGL((k_att_combine<128, EXTRA_UNSTAGE>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse, ex);
+    else
+        hipLaunchKernelGGL((k_att_combine<64, EXTRA_UNSTAGE>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse, ex);
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;
 }

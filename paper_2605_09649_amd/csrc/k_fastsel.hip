@@ -17,7 +17,7 @@
 // a list that is short (first call, a budget or workload change), too long for its buffer, or with too many equal
 // keys at the threshold makes the last block run a plain three-pass radix select over the sequence on its own
 // (slow - one block reads every score three times - but rare) which also re-seeds the bound.
-#include "kvtrim_device.h"
+#include "kvtrim_paged_device.h"
 
 namespace kvtrim {
 
@@ -408,6 +408,25 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
     __shared__ int s_seqcnt[STEP ? STEP_MAX_SEQS : 1];
     static_assert(STEP_MAX_SEGS <= FAST_STAGE && STEP_MAX_SEGS <= FAST_THREADS && STEP_MAX_EVICT <= FAST_STAGE, "the step's tables reuse the staging space, one segment per thread");
     const int tid = threadIdx.x;
+    // PAGED, when the caller attends next: behind the scanning blocks the grid has PG_TABLE_BLOCKS blocks that build the
+    // attention's chunk table.  The table depends on the block tables only, which this step's eviction leaves alone (a
+    // page that it empties stays listed until it is tidied away, and a reader finds all its slots empty).
+    if (PAGED && (int)blockIdx.x >= sh.nseg * bps) {
+        PagedView pc{};
+        pc.block_table = const_cast<int32_t*>(sa.pg.block_table);
+        pc.seg_pages = const_cast<int32_t*>(sa.pg.seg_pages);
+        pc.seg_live = const_cast<int32_t*>(sa.pg.seg_live);
+        pc.n_pages = sa.pg.n_pages;
+        pc.max_pps = sa.pg.max_pps;
+        const int H = sh.n_kv_heads, L = sh.n_layers, lb = sa.pg.plan_layer_begin, le = sa.pg.plan_layer_end;
+        auto in_range = [=](int g) {
+            const int layer = (g / H) % L;
+            return layer >= lb && layer < le;
+        };
+        build_page_table<ATT_PAGE_GROUP>(pc, sh.nseg, in_range, ws.att_chunk_prefix, ws.att_desc, ws.max_att_chunks, nullptr,
+                                         ws.err, (int)blockIdx.x - sh.nseg * bps, (int)gridDim.x - sh.nseg * bps, ws.att_pages);
+        return;
+    }
     // STEP: behind the scanning blocks the grid has one block per segment that only writes the segment's tables
     const bool tables_only = STEP && (int)blockIdx.x >= sh.nseg * bps;
     const int seg = tables_only ? (int)blockIdx.x - sh.nseg * bps : (int)blockIdx.x / bps;
@@ -1082,10 +1101,12 @@ kvtrim_status launch_score_select_paged(kvtrim_ctx* ctx, const CacheView& pool, 
     int64_t bps = pool.cap / ((int64_t)sh.nseg * FAST_ENTRIES_PER_BLOCK);
     bps = bps < 1 ? 1 : (bps > 64 ? 64 : bps);
     const dim3 grid((unsigned)(sh.nseg * bps)), block(FAST_THREADS);
+    const bool plan = pg.plan_layer_end > pg.plan_layer_begin;
+    const dim3 scan_grid((unsigned)(sh.nseg * bps + (plan ? PG_TABLE_BLOCKS : 0)));
     StepArgs sa{};
     sa.pg = pg;
     { ProfScope prof(ctx, K_FAST_SCAN, st);
-      hipLaunchKernelGGL((k_fast_scan<true, SCAN_PAGED>), grid, block, 0, st, pool, now, (const float*)nullptr, score, budget, sh, ws, (int)bps, kept, thr, sa); }
+      hipLaunchKernelGGL((k_fast_scan<true, SCAN_PAGED>), scan_grid, block, 0, st, pool, now, (const float*)nullptr, score, budget, sh, ws, (int)bps, kept, thr, sa); }
     { ProfScope prof(ctx, K_FAST_MASK, st);
       if (evict)
           hipLaunchKernelGGL((k_fast_mask<true, true>), grid, block, 0, st, pool, (const float*)score, sh, ws, (int)bps, keep, kept, pg);

@@ -474,33 +474,7 @@ constexpr int UNS_THREADS = 256;
 template <int D>
 __global__ __launch_bounds__(UNS_THREADS) void k_cmp_unstage(CacheViewMut c, CacheViewMut stage,
                                                              const int32_t* __restrict__ kept, Shape sh, Workspace ws) {
-    constexpr int VPR = D / 8;                                    // 16-byte vectors per row
-    const int lane = lane_id();
-    const int ch = blockIdx.x * (UNS_THREADS / 64) + (threadIdx.x >> 6);
-    if (__hip_atomic_load(ws.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
-    if (ch >= ws.cmp_chunk_prefix[sh.nseg]) return;
-    const ChunkDesc cd = ws.cmp_desc[ch];
-    const int seg = cd.seg;
-    const int64_t dbase = ws.cmp_chunk_dst[ch] & ~CMP_DST_FULL;
-    const int first_ch = ws.cmp_chunk_prefix[seg];
-    if (ch == first_ch && lane == 0) c.seg_len[seg] = kept[seg];
-    if (cd.first == dbase) return;                                // nothing was evicted before this chunk
-    const bool last = ch + 1 >= ws.cmp_chunk_prefix[seg + 1];
-    const int64_t dnext = last ? c.seg_start[seg] + kept[seg] : (ws.cmp_chunk_dst[ch + 1] & ~CMP_DST_FULL);
-    const int64_t staged = min(cd.first - dbase, dnext - dbase);  // survivors that belong before the chunk's own range
-    const uint4* sk = reinterpret_cast<const uint4*>(stage.k) + dbase * VPR;
-    const uint4* sv = reinterpret_cast<const uint4*>(stage.v) + dbase * VPR;
-    uint4* dk = reinterpret_cast<uint4*>(c.k) + dbase * VPR;
-    uint4* dv = reinterpret_cast<uint4*>(c.v) + dbase * VPR;
-    for (int64_t i = lane; i < staged * VPR; i += 64) {
-        dk[i] = sk[i];
-        dv[i] = sv[i];
-    }
-    for (int64_t i = lane; i < staged; i += 64) {
-        c.log_beta[dbase + i] = stage.log_beta[dbase + i];
-        if (c.log_tail) c.log_tail[dbase + i] = stage.log_tail[dbase + i];
-        c.pos[dbase + i] = stage.pos[dbase + i];
-    }
+    unstage_chunk<D>(c, stage, kept, sh, ws, (int)(blockIdx.x * (UNS_THREADS / 64) + (threadIdx.x >> 6)));
 }
 
 // Stage 3 alone inside the cache: k_cmp_attn<.., INPLACE> without the attention.  A chunk that loses nothing and
@@ -691,15 +665,8 @@ kvtrim_status launch_compact_attn_inplace(kvtrim_ctx* ctx, const CacheViewMut& c
                  : dispatch_fused<64, true>(sh.group, dim3((unsigned)max_chunks), st, src, keep, c, stage, q, sh, ws, scale_log2, layer_begin, layer_end);
     }
     if (!ok) return KVTRIM_EINVAL;
-    {
-        ProfScope prof(ctx, K_CMP_UNSTAGE, st);
-        const dim3 grid((unsigned)((max_chunks + UNS_THREADS / 64 - 1) / (UNS_THREADS / 64)));
-        if (sh.head_dim == 128)
-            hipLaunchKernelGGL(k_cmp_unstage<128>, grid, dim3(UNS_THREADS), 0, st, c, stage, kept, sh, ws);
-        else
-            hipLaunchKernelGGL(k_cmp_unstage<64>, grid, dim3(UNS_THREADS), 0, st, c, stage, kept, sh, ws);
-    }
-    return launch_combine(ctx, ws.cmp_chunk_prefix, layer_begin, layer_end, out, lse, st);
+    // the parked rows go to their places in the launch of the merge kernel (nothing there reads them)
+    return launch_combine_unstage(ctx, ws.cmp_chunk_prefix, layer_begin, layer_end, out, lse, c, stage, kept, max_chunks, st);
 }
 
 kvtrim_status launch_decode_step(kvtrim_ctx* ctx, const CacheViewMut& srcm, const StepArgs& sa, const int32_t* now,
@@ -780,15 +747,8 @@ kvtrim_status launch_decode_step_inplace(kvtrim_ctx* ctx, const CacheViewMut& c,
             default: return KVTRIM_EINVAL;
         }
     }
-    {
-        ProfScope prof(ctx, K_CMP_UNSTAGE, st);
-        const dim3 grid((unsigned)((max_chunks + UNS_THREADS / 64 - 1) / (UNS_THREADS / 64)));
-        if (sh.head_dim == 128)
-            hipLaunchKernelGGL(k_cmp_unstage<128>, grid, dim3(UNS_THREADS), 0, st, c, stage, kept, sh, ws);
-        else
-            hipLaunchKernelGGL(k_cmp_unstage<64>, grid, dim3(UNS_THREADS), 0, st, c, stage, kept, sh, ws);
-    }
-    return launch_combine(ctx, ws.cmp_chunk_prefix, layer_begin, layer_end, out, lse, st);
+    // the parked rows go to their places in the launch of the merge kernel (nothing there reads them)
+    return launch_combine_unstage(ctx, ws.cmp_chunk_prefix, layer_begin, layer_end, out, lse, c, stage, kept, max_chunks, st);
 }
 
 }  // namespace kvtrim

@@ -7,28 +7,9 @@
 // to pages: building them from a ragged cache, appending into free slots, the chunk tables, the
 // tie rule by position (a segment's slots are in no particular order), eviction and the
 // bookkeeping of free pages.
-#include "kvtrim_device.h"
+#include "kvtrim_paged_device.h"
 
 namespace kvtrim {
-
-constexpr int P = KVTRIM_PAGE_SIZE;
-
-struct PagedView {
-    uint16_t* k;
-    uint16_t* v;
-    float* log_beta;
-    int32_t* pos;
-    float* log_tail;
-    int32_t* block_table;
-    int32_t* seg_pages;
-    int32_t* seg_live;
-    int32_t* page_owner;
-    int32_t* page_live;
-    int32_t* free_list;
-    int32_t* n_free;
-    int32_t n_pages;
-    int32_t max_pps;
-};
 
 // ---------------------------------------------------------------------------------------------
 // Build: the page-aligned compaction has written the survivors of segment g to the slots
@@ -332,115 +313,7 @@ __global__ __launch_bounds__(PG4_THREADS) void k_pg_score(PagedView pc, const in
     *reinterpret_cast<float4*>(score + e) = r;
 }
 
-// ---------------------------------------------------------------------------------------------
-// Chunk table of a paged cache: the pages of every segment with in_range(g), in segment order,
-// GROUP pages to a chunk.  prefix[g] = first chunk of segment g, prefix[nseg] = number of chunks;
-// entry_prefix (optional) counts the live entries of the segments before g.
-//   GROUP == 1: desc = {first slot of the page, page size, segment}           (selection)
-//   GROUP  > 1: desc = {index of the group's first block-table entry, slots of the group, segment},
-//               pages_out[chunk][GROUP] = the group's pages (clamped into the pool; ATT_PAGE_FULL set when
-//               every slot of the page is live), so that the reader has them with the descriptor and
-//               not one dependent load later                                  (attention)
-// Built by `nparts` blocks: every block scans the per-segment counts (a few thousand integers),
-// block `part` fills the descriptors of the segments g = part (mod nparts), one wavefront per
-// segment, and block 0 writes the prefixes.  Returns the number of chunks.  Counts that do not
-// fit raise ERR_LAYOUT and leave the table empty; a page id out of range raises it too and is
-// clamped, so that no reader leaves the pool.
-template <int GROUP, typename InRange>
-__device__ __forceinline__ int build_page_table(const PagedView& pc, int nseg, InRange in_range, int32_t* prefix,
-                                                ChunkDesc* desc, int64_t max_chunks, int64_t* entry_prefix,
-                                                int32_t* err, int part, int nparts, int32_t* pages_out = nullptr) {
-    __shared__ uint64_t s_scan[17];
-    __shared__ int s_bad;
-    __shared__ int s_c0[1024], s_n[1024];
-    const int tid = threadIdx.x;
-    if (tid == 0) s_bad = 0;
-    __syncthreads();
-    uint64_t carry = 0;
-    for (int base = 0; base < nseg; base += blockDim.x) {
-        const int g = base + tid;
-        uint64_t v = 0;
-        int npg = 0;
-        if (g < nseg) {
-            npg = pc.seg_pages[g];
-            const int live = pc.seg_live[g];
-            if (npg < 0 || npg > pc.max_pps || live < 0 || (int64_t)live > (int64_t)npg * P) {
-                s_bad = 1;
-                npg = 0;
-            } else if (in_range(g)) {
-                v = ((uint64_t)live << 32) | (uint64_t)((npg + GROUP - 1) / GROUP);
-            } else {
-                npg = 0;
-            }
-        }
-        uint64_t tot;
-        const uint64_t ex = carry + block_excl_scan<uint64_t>(v, s_scan, &tot);
-        carry += tot;
-        const int c0 = (int)(ex & 0xffffffffu);
-        if (g < nseg && part == 0) {
-            prefix[g] = c0;
-            if (entry_prefix) entry_prefix[g] = (int64_t)(ex >> 32);
-        }
-        s_c0[tid] = c0;
-        s_n[tid] = npg;
-        __syncthreads();
-        if (!s_bad && (int64_t)(carry & 0xffffffffu) <= max_chunks) {
-            const int lane = lane_id(), wave = tid >> 6, nw = blockDim.x >> 6;
-            const int ntile = min((int)blockDim.x, nseg - base);
-            const int first_t = ((part - base) % nparts + nparts) % nparts;      // first t with (base + t) = part (mod nparts)
-            for (int t = first_t + wave * nparts; t < ntile; t += nw * nparts) {
-                const int gg = base + t, cc = s_c0[t], nn = s_n[t];
-                const int64_t row = (int64_t)gg * pc.max_pps;
-                bool bad_page = false;
-                for (int i = lane; i < nn; i += 64) {
-                    const int pg = pc.block_table[row + i];
-                    bad_page |= pg < 0 || pg >= pc.n_pages;
-                    ChunkDesc d;
-                    d.seg = gg;
-                    if (GROUP == 1) {
-                        d.first = (int64_t)min(max(pg, 0), pc.n_pages - 1) * P;
-                        d.n = P;
-                        desc[cc + i] = d;
-                    } else {
-                        if (pages_out) {                          // (a page without an empty slot is flagged: its reader skips the positions)
-                            const int pgc = min(max(pg, 0), pc.n_pages - 1);
-                            pages_out[(int64_t)(cc + i / GROUP) * GROUP + i % GROUP] = pgc | (pc.page_live[pgc] == P ? ATT_PAGE_FULL : 0);
-                        }
-                        if (i % GROUP == 0) {
-                            d.first = row + i;
-                            d.n = P * min(GROUP, nn - i);
-                            desc[cc + i / GROUP] = d;
-                        }
-                    }
-                }
-                if (__any(bad_page) && lane == 0) atomicOr(err, ERR_LAYOUT);
-            }
-        }
-        __syncthreads();
-    }
-    const int64_t total = (int64_t)(carry & 0xffffffffu);
-    if (s_bad || total > max_chunks) {
-        if (part == 0) {
-            if (tid == 0) atomicOr(err, ERR_LAYOUT);
-            for (int g = tid; g <= nseg; g += blockDim.x) {
-                prefix[g] = 0;
-                if (entry_prefix) entry_prefix[g] = 0;
-            }
-        }
-        __syncthreads();
-        return 0;
-    }
-    if (tid == 0 && part == 0) {
-        prefix[nseg] = (int32_t)total;
-        if (entry_prefix) entry_prefix[nseg] = (int64_t)(carry >> 32);
-    }
-    __syncthreads();
-    return (int)total;
-}
-
-constexpr int PG_TABLE_BLOCKS = 16;
 constexpr int PG_PLAN_ZERO_BLOCKS = 8;
-constexpr int ATT_PAGE_GROUP = 4;          // pages per attention chunk (512 rows, the ragged path's chunk)
 
 // segment that owns chunk c: the last g with prefix[g] <= c (prefix[nseg] > c)
 __device__ __forceinline__ int seg_of_chunk(const int32_t* prefix, int nseg, int c) {
@@ -711,8 +584,8 @@ __global__ __launch_bounds__(PGC_THREADS) void k_pg_count(PagedView pc, const fl
 // ---------------------------------------------------------------------------------------------
 // Eviction: a block takes PG_PER_BLOCK pages, a thread four consecutive slots (16-byte loads of the
 // positions, 4-byte loads of the mask), so a page is the business of one half wavefront.  A page left
-// without a live entry is marked for release (owner -2); k_pg_tidy takes it out of its segment's block
-// table and pushes it on the free list.
+// without a live entry is marked for release (owner -2); tidying (k_pg_tidy, or the tidy blocks of the
+// attention's merge kernel) takes it out of its segment's block table and pushes it on the free list.
 __global__ __launch_bounds__(PG4_THREADS) void k_pg_evict(PagedView pc, const uint8_t* __restrict__ keep, int nseg) {
     const int page = blockIdx.x * PG_PER_BLOCK + (threadIdx.x >> 5);
     const int owner = page < pc.n_pages ? pc.page_owner[page] : -1;
@@ -743,45 +616,8 @@ __global__ __launch_bounds__(PG4_THREADS) void k_pg_evict(PagedView pc, const ui
     }
 }
 
-// One block per segment: drops the pages marked for release from the block table (order of the
-// others kept) and returns them to the free list.
-__global__ __launch_bounds__(256) void k_pg_tidy(PagedView pc, int32_t* err) {
-    __shared__ int32_t lds32[17];
-    __shared__ int32_t s_page[256];
-    const int g = blockIdx.x, tid = threadIdx.x;
-    const int npg = pc.seg_pages[g];
-    if (npg < 0 || npg > pc.max_pps) {
-        if (tid == 0) atomicOr(err, ERR_LAYOUT);
-        return;
-    }
-    int32_t* bt = pc.block_table + (int64_t)g * pc.max_pps;
-    int out = 0;
-    for (int base = 0; base < npg; base += 256) {                    // read a tile, then write it: out <= base
-        const int i = base + tid;
-        int page = -1;
-        bool alive = false;
-        if (i < npg) {
-            page = bt[i];
-            if (page >= 0 && page < pc.n_pages) {
-                alive = pc.page_owner[page] == g;
-                if (!alive && pc.page_owner[page] == -2) {          // release
-                    pc.page_owner[page] = -1;
-                    pc.page_live[page] = 0;
-                    const int idx = atomicAdd(pc.n_free, 1);
-                    if (idx >= 0 && idx < pc.n_pages) pc.free_list[idx] = page;
-                }
-            }
-        }
-        int32_t tot;
-        const int32_t ex = block_excl_scan<int32_t>(alive ? 1 : 0, lds32, &tot);
-        s_page[tid] = page;
-        __syncthreads();
-        if (alive) bt[out + ex] = s_page[tid];
-        __syncthreads();
-        out += tot;
-    }
-    if (tid == 0) pc.seg_pages[g] = out;
-}
+// One block per segment: the pages that an eviction emptied leave the segment's block table.
+__global__ __launch_bounds__(256) void k_pg_tidy(PagedView pc, int32_t* err) { tidy_segment<256>(pc, blockIdx.x, err); }
 
 // ---------------------------------------------------------------------------------------------
 // Defragmentation (housekeeping of the paged layout, not a step of the method): eviction frees a page only
@@ -916,6 +752,18 @@ static CacheView pool_view(const kvtrim_paged_cache* c) {
     v.cap = (int64_t)c->n_pages * P;
     v.log_tail = c->log_tail;
     return v;
+}
+
+// what is wrong with the arguments of an attention call over pages (NULL if nothing)
+static const char* paged_attn_problem(const kvtrim_ctx* ctx, const kvtrim_paged_cache* c, const void* q, int32_t layer_begin,
+                                      int32_t layer_end, float softmax_scale, const float* out) {
+    if (!q || !out) return "q / out is NULL";
+    if (((uintptr_t)q) & 15) return "q not 16-byte aligned";
+    if (layer_begin < 0 || layer_end > ctx->cfg.n_layers || layer_begin >= layer_end) return "empty or out-of-range layer range";
+    if (!(softmax_scale == softmax_scale)) return "softmax_scale is NaN";
+    if ((int64_t)c->n_pages / ATT_PAGE_GROUP + ctx->shape.nseg > ctx->ws.max_att_chunks)
+        return "too many pages for the partial-result buffer of this context";
+    return nullptr;
 }
 
 static const char* paged_problem(const kvtrim_ctx* ctx, const kvtrim_paged_cache* c) {
@@ -1066,7 +914,7 @@ kvtrim_status kvtrim_paged_score_select(kvtrim_ctx* ctx, const kvtrim_paged_cach
         if (rc != KVTRIM_OK) return rc;
         return kvtrim_paged_select(ctx, c, score_out, budget, keep_out, kept_out, thr_key_out, hip_stream);
     }
-    PagedArgs pg;
+    PagedArgs pg{};
     pg.block_table = c->block_table;
     pg.seg_pages = c->seg_pages;
     pg.seg_live = c->seg_live;
@@ -1091,11 +939,11 @@ kvtrim_status kvtrim_paged_decode_step(kvtrim_ctx* ctx, kvtrim_paged_cache* c, c
         rc = kvtrim_paged_evict(ctx, c, keep_out, hip_stream);
         if (rc != KVTRIM_OK) return rc;
     } else {
-        // the decode-step selection, whose mask kernel also applies the eviction; then the emptied pages leave the tables
+        // the decode-step selection, whose mask kernel also applies the eviction ...
         if (!now || !budget || !score_out || !keep_out || !kept_out) return bad(ctx, "now / budget / score_out / keep_out / kept_out is NULL");
         if ((((uintptr_t)score_out) & 15) || (((uintptr_t)keep_out) & 3)) return bad(ctx, "score_out not 16-byte or keep_out not 4-byte aligned");
         hipStream_t st = (hipStream_t)hip_stream;
-        PagedArgs pg;
+        PagedArgs pg{};
         pg.block_table = c->block_table;
         pg.seg_pages = c->seg_pages;
         pg.seg_live = c->seg_live;
@@ -1105,11 +953,17 @@ kvtrim_status kvtrim_paged_decode_step(kvtrim_ctx* ctx, kvtrim_paged_cache* c, c
         pg.evict_seg_live = c->seg_live;
         pg.evict_page_live = c->page_live;
         pg.evict_page_owner = c->page_owner;
+        // ... whose scoring kernel also builds the attention's chunk table; the merge kernel of the attention tidies
+        // the block tables afterwards: five kernels in all
+        if (const char* p = paged_attn_problem(ctx, c, q, layer_begin, layer_end, softmax_scale, out)) return bad(ctx, p);
+        pg.plan_layer_begin = layer_begin;
+        pg.plan_layer_end = layer_end;
         rc = launch_score_select_paged(ctx, pool_view(c), pg, now, budget, score_out, keep_out, kept_out, thr_key_out, st, true);
         if (rc != KVTRIM_OK) return rc;
-        ProfScope prof(ctx, K_PG_TIDY, st);
-        hipLaunchKernelGGL(k_pg_tidy, dim3(ctx->shape.nseg), dim3(256), 0, st, view_of(c), ctx->ws.err);
-        KVTRIM_HIP(ctx, hipGetLastError());
+        const PagedView pv = view_of(c);
+        const int max_chunks = c->n_pages / ATT_PAGE_GROUP + ctx->shape.nseg;
+        return launch_attn_paged(ctx, pool_view(c), c->block_table, (const uint16_t*)q, max_chunks, layer_begin, layer_end,
+                                 softmax_scale, out, lse, st, &pv);
     }
     return kvtrim_paged_attn(ctx, c, q, layer_begin, layer_end, softmax_scale, out, lse, hip_stream);
 }
@@ -1151,13 +1005,7 @@ kvtrim_status kvtrim_paged_attn(kvtrim_ctx* ctx, const kvtrim_paged_cache* c, co
                                 int32_t layer_end, float softmax_scale, float* out, float* lse, void* hip_stream) {
     if (!ctx) return KVTRIM_EINVAL;
     if (const char* p = paged_problem(ctx, c)) return bad(ctx, p);
-    if (!q || !out) return bad(ctx, "q / out is NULL");
-    if (((uintptr_t)q) & 15) return bad(ctx, "q not 16-byte aligned");
-    if (layer_begin < 0 || layer_end > ctx->cfg.n_layers || layer_begin >= layer_end)
-        return bad(ctx, "empty or out-of-range layer range");
-    if (!(softmax_scale == softmax_scale)) return bad(ctx, "softmax_scale is NaN");
-    if ((int64_t)c->n_pages / ATT_PAGE_GROUP + ctx->shape.nseg > ctx->ws.max_att_chunks)
-        return bad(ctx, "too many pages for the partial-result buffer of this context");
+    if (const char* p = paged_attn_problem(ctx, c, q, layer_begin, layer_end, softmax_scale, out)) return bad(ctx, p);
     hipStream_t st = (hipStream_t)hip_stream;
     {
         ProfScope prof(ctx, K_PG_ATT_PLAN, st);

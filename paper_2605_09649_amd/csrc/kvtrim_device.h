@@ -196,4 +196,40 @@ __device__ __forceinline__ int build_chunk_table(const int32_t* __restrict__ seg
     return (int)total;
 }
 
+// After the in-place row mover: the survivors of chunk `ch` whose place lies before the chunk's own range (as many
+// as were evicted before the chunk in its segment, at most all of its survivors) wait in `stage` at their final
+// index; the calling wavefront puts them there (in a decode step most chunks have nothing parked and the call
+// returns at once).  The wavefront of a segment's first chunk also commits the segment's new length, which no
+// kernel of the call reads any more.
+template <int D>
+__device__ __forceinline__ void unstage_chunk(const CacheViewMut& c, const CacheViewMut& stage, const int32_t* __restrict__ kept,
+                                              const Shape& sh, const Workspace& ws, int ch) {
+    constexpr int VPR = D / 8;                                    // 16-byte vectors per row
+    const int lane = lane_id();
+    if (__hip_atomic_load(ws.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;
+    if (ch >= ws.cmp_chunk_prefix[sh.nseg]) return;
+    const ChunkDesc cd = ws.cmp_desc[ch];
+    const int seg = cd.seg;
+    const int64_t dbase = ws.cmp_chunk_dst[ch] & ~CMP_DST_FULL;
+    const int first_ch = ws.cmp_chunk_prefix[seg];
+    if (ch == first_ch && lane == 0) c.seg_len[seg] = kept[seg];
+    if (cd.first == dbase) return;                                // nothing was evicted before this chunk
+    const bool last = ch + 1 >= ws.cmp_chunk_prefix[seg + 1];
+    const int64_t dnext = last ? c.seg_start[seg] + kept[seg] : (ws.cmp_chunk_dst[ch + 1] & ~CMP_DST_FULL);
+    const int64_t staged = min(cd.first - dbase, dnext - dbase);  // survivors that belong before the chunk's own range
+    const uint4* sk = reinterpret_cast<const uint4*>(stage.k) + dbase * VPR;
+    const uint4* sv = reinterpret_cast<const uint4*>(stage.v) + dbase * VPR;
+    uint4* dk = reinterpret_cast<uint4*>(c.k) + dbase * VPR;
+    uint4* dv = reinterpret_cast<uint4*>(c.v) + dbase * VPR;
+    for (int64_t i = lane; i < staged * VPR; i += 64) {
+        dk[i] = sk[i];
+        dv[i] = sv[i];
+    }
+    for (int64_t i = lane; i < staged; i += 64) {
+        c.log_beta[dbase + i] = stage.log_beta[dbase + i];
+        if (c.log_tail) c.log_tail[dbase + i] = stage.log_tail[dbase + i];
+        c.pos[dbase + i] = stage.pos[dbase + i];
+    }
+}
+
 }  // namespace kvtrim

@@ -94,6 +94,8 @@ struct PagedArgs {
     int32_t* evict_seg_live;
     int32_t* evict_page_live;
     int32_t* evict_page_owner;
+    // layers [plan_layer_begin, plan_layer_end) whose attention chunk table the scoring kernel also builds (none: no table)
+    int32_t plan_layer_begin, plan_layer_end;
 };
 
 // The decode step in one call (kvtrim_decode_step): the tokens that enter the cache in this step (laid out as kvtrim_append takes them;
@@ -114,7 +116,6 @@ struct StepArgs {
     bool inplace;                // the compaction happens inside src (every segment keeps its start; dst is not used)
 };
 
-constexpr int ATT_PAGE_FULL = 0x40000000;   // in ws.att_pages: the page has no empty slot
 // One-call decode step: per segment, where its survivors start in the destination and which of its entries go -
 // the first STEP_REC_IDX of them here, all of them in ws.step_evl from `off` on (index in the sequence's part).
 constexpr int STEP_REC_IDX = 12;
@@ -168,7 +169,7 @@ struct Workspace {
     int32_t* cmp_chunk_prefix;   // [nseg+1]
     ChunkDesc* cmp_desc;         // [max_cmp_chunks]
     int64_t* cmp_chunk_dst;      // [max_cmp_chunks] first dst entry of the chunk's survivors (| CMP_DST_FULL)
-    int32_t* att_pages;          // [max_att_chunks][4] paged attention: the pages of a chunk, beside its descriptor (| ATT_PAGE_FULL)
+    int32_t* att_pages;          // [max_att_chunks][4] paged attention: the pages of a chunk, beside its descriptor
     // attention
     int32_t* att_chunk_prefix;   // [nseg+1]
     ChunkDesc* att_desc;         // [max_att_chunks]
@@ -265,10 +266,12 @@ kvtrim_status launch_attn(kvtrim_ctx*, const CacheView&, const uint16_t* q, cons
                           int32_t layer_begin, int32_t layer_end, float scale, float* out, float* lse, hipStream_t);
 void launch_select_passes_paged(kvtrim_ctx*, const float* score, const SelTables&, int hist_blocks, int pass,
                                 uint32_t* thr, hipStream_t);
+struct PagedView;
+// tidy: the merge kernel's launch also takes the pages that an eviction emptied out of the block tables
 kvtrim_status launch_attn_paged(kvtrim_ctx*, const CacheView& pool, const int32_t* block_table, const uint16_t* q,
                                 int max_chunks,
                                 int32_t layer_begin, int32_t layer_end, float scale, float* out, float* lse,
-                                hipStream_t);
+                                hipStream_t, const PagedView* tidy = nullptr);
 // gat: also writes the table of the DESTINATION's CMP_CHUNK-row chunks (ws.att_chunk_prefix / ws.att_desc) and the source
 // row of every destination row (ws.gat_src) - what the gathering instance of the fused kernel reads.
 void launch_cmp_scan_aligned(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const int32_t* kept,
@@ -291,6 +294,10 @@ void launch_cmp_scan(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, con
                      const CacheViewMut& dst, int32_t reserve, hipStream_t);
 kvtrim_status launch_combine(kvtrim_ctx*, const int32_t* chunk_prefix, int32_t layer_begin, int32_t layer_end,
                              float* out, float* lse, hipStream_t);
+// ... whose launch also finishes an in-place compaction: the rows parked in `stage` go to their places
+kvtrim_status launch_combine_unstage(kvtrim_ctx*, const int32_t* chunk_prefix, int32_t layer_begin, int32_t layer_end,
+                                     float* out, float* lse, const CacheViewMut& c, const CacheViewMut& stage,
+                                     const int32_t* kept, int64_t max_chunks, hipStream_t);
 void launch_cmp_scan_inplace(kvtrim_ctx*, const CacheViewMut& c, const uint8_t* keep, const int32_t* kept, hipStream_t);
 // Stage 3 alone inside the cache itself.
 kvtrim_status launch_compact_inplace(kvtrim_ctx*, const CacheViewMut& c, const uint8_t* keep, const int32_t* kept,
