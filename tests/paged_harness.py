@@ -137,14 +137,15 @@ def ties_overflow(w, hc, score_ref, live, thr_ref, budget_np):
 
 
 def run_paged_both(w, budgets, device="cuda:0", cache_dict=None, now0=None, n_pages=None, max_pps=None, horizon=1,
-                   tweak_new=None, defrag_at=(), hint=None, one_call=False):
+                   tweak_new=None, defrag_at=(), hint=None, one_call=False, layer_range=None):
     """budgets: one per-sequence budget list per step; step 0 selects on the ragged prefill cache
     and builds the pages, the later steps run on the pages.  tweak_new(step, inputs) may edit the
     generated inputs of a step (used to plant ties).  In the steps listed in defrag_at the pages are
     defragmented between eviction and attention.  hint: None runs stages 1 and 2 on the pages as two calls,
     a number runs kvtrim_paged_score_select with that evict_hint.  one_call: the paged steps run
-    kvtrim_paged_decode_step (append, score_select, evict and attention in one call; hint required).  Returns one dict of
-    findings per step."""
+    kvtrim_paged_decode_step (append, score_select, evict and attention in one call; hint required).  layer_range
+    (one_call only): the steps on the pages attend these layers only - their rows are compared, and the other rows of
+    `out` and `lse` must stay as they were.  Returns one dict of findings per step."""
     reserve = 1
     if cache_dict is None:
         cache_dict = ki.prefill_cache(w, reserve=reserve)
@@ -205,8 +206,12 @@ def run_paged_both(w, budgets, device="cuda:0", cache_dict=None, now0=None, n_pa
             res["keep_equal"] = bool(np.array_equal(keep[:hc.cap].cpu().numpy()[live], keep_ref[live]))
         elif one_call:
             pos_before = pc.pos.clone()
+            lb, le = layer_range if layer_range is not None else (0, w.n_layers)
+            if layer_range is not None:
+                out.fill_(7.0)
+                lse.fill_(7.0)
             kv.kvtrim_paged_decode_step(ctx, pc, d["k_new"], d["v_new"], d["log_beta_new"], pos_dev, now_dev, budget_dev, score, keep,
-                                        kept, d["q"], 0, w.n_layers, scale, out, lse, thr_key_out=thr,
+                                        kept, d["q"], lb, le, scale, out, lse, thr_key_out=thr,
                                         log_tail_new=d.get("log_tail_new"), evict_hint=hint)
             res["status_select"] = kv.kvtrim_poll_error(ctx)
             # the evicted slots are empty already: scores and mask are checked on the survivors (matched through their
@@ -254,7 +259,14 @@ def run_paged_both(w, budgets, device="cuda:0", cache_dict=None, now0=None, n_pa
         ph = PagedHost(pc)
         res["structure"] = ph.structure_problems()
         res["cache_equal"] = ph.equals(hc_next)
-        res.update(attn_result(out.cpu().numpy(), lse.cpu().numpy(), out_ref, lse_ref))
+        if one_call and step > 0 and layer_range is not None:
+            lb, le = layer_range
+            o, l = out.cpu().numpy(), lse.cpu().numpy()
+            outside = [x for x in range(w.n_layers) if not lb <= x < le]
+            res["untouched_outside_range"] = bool((o[:, outside] == 7.0).all() and (l[:, outside] == 7.0).all())
+            res.update(attn_result(o[:, lb:le], l[:, lb:le], out_ref[:, lb:le], lse_ref[:, lb:le]))
+        else:
+            res.update(attn_result(out.cpu().numpy(), lse.cpu().numpy(), out_ref, lse_ref))
         res["kept_total"] = int(kept_ref.sum())
         res["pages_in_use"] = int(ph.seg_pages.sum())
         res["ties_overflow"] = ties_overflow(w, hc, score_ref, live, thr_ref, budget_np)

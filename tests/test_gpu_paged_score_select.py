@@ -186,6 +186,20 @@ def test_one_call_pages_are_freed_and_taken_again():
     assert min(pages) == 0 and pages[-1] == w.nseg and max(pages[:44]) > min(pages[44:60]) and listed >= 30, (pages, listed, fallback)
 
 
+@pytest.mark.parametrize("layer_range", [(1, 2), (0, 2), (2, 3)])
+def test_one_call_layer_range_paged(layer_range):
+    # the step's scoring kernel builds the attention's chunk table for the layers asked for only: their rows of `out`
+    # equal the oracle's, the other rows stay as they were, and every segment is scored, evicted and tidied all the same
+    w = wl(2, 3, 2, 4, 128)
+    seg_len = [400, 130, 700, 5, 256, 300, 0, 128, 129, 640, 50, 900]
+    c, now = ki.ragged_cache(w, seg_len, reserve=1, salt=8)
+    budget = [sum(seg_len[:6]) - 30, sum(seg_len[6:]) - 200]
+    res = run_paged_both(w, [budget] * 5, device=DEV, cache_dict=c, now0=now.numpy(), hint=12, one_call=True,
+                         layer_range=layer_range)
+    check(res)
+    assert all(r["untouched_outside_range"] for r in res[1:]), res
+
+
 @pytest.mark.parametrize("horizon", [2, 0])
 def test_one_call_lookahead_horizon_paged(horizon):
     w = ki.workload("tiny", prefill=700)
