@@ -1,7 +1,8 @@
 // Stage 4: GQA decode attention over the ragged retained caches (Sec. 2.1, Eq. reform, r in {0,1}).
 //
 // Split-K over fixed-size chunks of each segment so that very unequal segment lengths still
-// fill the chip.  Inside a chunk a wavefront walks tiles of 16 rows:
+// fill the chip: a fixed grid of blocks shares the rows of the chunk table equally, each block
+// walking a contiguous stretch of it.  Inside a chunk a wavefront walks tiles of 16 rows:
 //   Q.K^T  one MFMA 16x16 accumulator per tile (rows = 16 keys, columns = the G query heads,
 //          padded to 16); K fragments are loaded straight from HBM in the operand layout
 //          (lane = key row, four lanes share 64 contiguous bytes of the row).
@@ -11,8 +12,9 @@
 //          the MFMA's reduction dimension; the probabilities of those rows for query head c are
 //          what the Q.K^T accumulator of lane (b, c) holds - the other operand, as two bf16 terms.
 // A wavefront keeps one online-softmax stream per query head (the maximum over the tile's 16
-// rows); at the end of the chunk the four wavefronts are merged through LDS, and the chunks of
-// a segment by k_att_combine.  Logits are kept in base-2 units.
+// rows) for as long as the block stays inside one segment; then the four wavefronts are merged
+// through LDS, and the partial results of a segment by k_att_combine.  Logits are kept in base-2
+// units.
 #include "kvtrim_paged_device.h"
 
 namespace kvtrim {
@@ -68,7 +70,7 @@ struct Frag<64> {
     static __device__ __forceinline__ unsigned word(vec x, int w) { return w == 0 ? x.x : x.y; }
 };
 
-// partial layout: [chunk][G][D + 2] = (m in base-2 units, l, o[D] unnormalised)
+// partial layout: [slot][G][D + 2] = (m in base-2 units, l, o[D] unnormalised)
 // SOFT: retention-gated attention of Sec. 2.2 - the logit of entry i gets the bias (t - i) log(beta_i),
 // t = now[seq] (the weights beta^(t-i) e^z of the soft form); otherwise hard eviction, no bias.
 // PAGED: the chunk is a run of pages of a paged cache - cd.first indexes the first of them in the block
@@ -77,7 +79,8 @@ struct Frag<64> {
 template <int D, int G, bool SOFT, bool PAGED>
 __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const uint16_t* __restrict__ q,
                                                              Shape sh, Workspace ws, int chunk,
-                                                             float scale_log2, const int32_t* __restrict__ now) {
+                                                             float scale_log2, const int32_t* __restrict__ now,
+                                                             int rpc, int extra_base) {
     typedef Frag<D> F;
     typedef typename F::vec vec;
     constexpr int E = F::E;
@@ -87,36 +90,110 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
     __shared__ __attribute__((aligned(16))) float s_o[NSTREAM][G][SO];
 
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
-    const int ch = blockIdx.x;                                    // (the grid never exceeds the tables)
+    // The grid is fixed (a few blocks per compute unit).  Every chunk of the table (T chunks of `chunk` rows, ragged
+    // ones at the segments' ends) counts as rpc parts of chunk / rpc rows; block b walks the parts [b V / nb, (b + 1) V / nb),
+    // V = T rpc, so the blocks' shares differ by one part at most, and keeps ONE online-softmax state for as long as
+    // its parts belong to the same segment: a partial result is written per (block, segment) run and not per chunk -
+    // at the slot of the run's first chunk, or at slot extra_base + b when the run starts inside a chunk (which only a
+    // block's first chunk can do; the block before it owns that chunk's slot).
+    // On this GPU a stream of reads slows down by far more than the bytes suggest when result writes are mixed into
+    // it (8.5 MB of writes in a 1.1 GB read stream cost 12 us of 170), so the fewer partial results the better.
     const int total = ws.att_chunk_prefix[sh.nseg];
-    const ChunkDesc cd = ws.att_desc[ch];                         // requested together with the count ...
-    int4 pgs = make_int4(0, 0, 0, 0);
-    if (PAGED) pgs = reinterpret_cast<const int4*>(ws.att_pages)[ch];   // ... and with the chunk's pages
-    if (ch >= total) return;
-    const int seg = cd.seg;
-    const int off = 0, row_end = cd.n;                            // rows [0, n) counted from cd.first
-    const int64_t base = cd.first;
+    const int nb = min((int)gridDim.x, total);
+    if ((int)blockIdx.x >= nb) return;
+    const int64_t V = (int64_t)total * rpc;
+    const int64_t v_begin = (int64_t)blockIdx.x * V / nb, v_end = (int64_t)(blockIdx.x + 1) * V / nb;   // (at least rpc parts)
+    const int ch_begin = (int)(v_begin / rpc), ch_last = (int)((v_end - 1) / rpc);
+    const int part_rows = chunk / rpc;
     const int c16 = lane & 15, b4 = lane >> 4;
-
-    // query fragments: lane (query c16, k-group b4), MFMA step j covers elements (4j + b4)*E ..
-    const int seq = seg / sh.segs_per_seq, lh = seg % sh.segs_per_seq;
-    const int layer = lh / sh.n_kv_heads, head = lh % sh.n_kv_heads;
-    const int64_t qrow = ((int64_t)seq * sh.n_layers + layer) * sh.n_q_heads + (int64_t)head * G + c16;
-    vec qf[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-        qf[j] = c16 < G ? reinterpret_cast<const vec*>(q + qrow * D)[4 * j + b4] : F::zero();
-
-    // o[e][i] = unnormalised output of head c16, column E (4 b4 + i) + e (the MFMA accumulators of P.V)
-    float4v o[E];
-#pragma unroll
-    for (int e = 0; e < E; ++e) o[e] = float4v{0.f, 0.f, 0.f, 0.f};
-    float m = -INFINITY, l = 0.f;                                 // m: running maximum of head c16 (the same in the four row groups)
-    const int t_now = SOFT ? now[seq] : 0;
-
     const vec* kp = reinterpret_cast<const vec*>(c.k);
     const vec* vp = reinterpret_cast<const vec*>(c.v);
     constexpr int VPR = D / E;                                    // vectors per row = 16
+
+    // o[e][i] = unnormalised output of head c16, column E (4 b4 + i) + e (the MFMA accumulators of P.V)
+    float4v o[E];
+    float m, l;                                                   // m: running maximum of head c16 (the same in the four row groups)
+    vec qf[4];
+    int t_now = 0;
+    auto reset = [&]() {
+#pragma unroll
+        for (int e = 0; e < E; ++e) o[e] = float4v{0.f, 0.f, 0.f, 0.f};
+        m = -INFINITY;
+        l = 0.f;
+    };
+    // the run's partial result goes to slot `slot`: the wavefronts' partials (the MFMAs have summed over a wavefront's
+    // row groups already) meet in LDS, s_o[wave][head][(4 i + b4) E + e] = column E (4 b4 + i) + e, and are merged
+    auto flush = [&](int slot) {
+        float l_all = l;
+        l_all += __shfl_xor(l_all, 16, 64);
+        l_all += __shfl_xor(l_all, 32, 64);
+        if (c16 < G) {
+            if (b4 == 0) {
+                s_m[wave][c16] = m;
+                s_l[wave][c16] = l_all;
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float* so = &s_o[wave][c16][(4 * i + b4) * E];
+#pragma unroll
+                for (int e4 = 0; e4 < E; e4 += 4)
+                    *reinterpret_cast<float4*>(so + e4) = make_float4(o[e4][i], o[e4 + 1][i], o[e4 + 2][i], o[e4 + 3][i]);
+            }
+        }
+        __syncthreads();
+        float* part = ws.att_partial + (size_t)slot * G * (D + 2);
+        for (int idx = tid; idx < G * D; idx += ATT_THREADS) {
+            const int g = idx / D, d = idx % D;
+            const int cb = d / E;
+            const int so_at = (4 * (cb & 3) + (cb >> 2)) * E + d % E;
+            float M = -INFINITY;
+#pragma unroll
+            for (int s2 = 0; s2 < NSTREAM; ++s2) M = fmaxf(M, s_m[s2][g]);
+            const float Ms = M == -INFINITY ? 0.f : M;
+            float accd = 0.f, lsum = 0.f;
+#pragma unroll
+            for (int s2 = 0; s2 < NSTREAM; ++s2) {
+                const float w = __builtin_amdgcn_exp2f(s_m[s2][g] - Ms);
+                accd += s_o[s2][g][so_at] * w;
+                lsum += s_l[s2][g] * w;
+            }
+            part[g * (D + 2) + 2 + d] = accd;
+            if (d == 0) {
+                part[g * (D + 2)] = M;
+                part[g * (D + 2) + 1] = lsum;
+            }
+        }
+        __syncthreads();                                          // (the next run's partials may overwrite LDS)
+    };
+    reset();
+    int cur_seg = -1, run_first = ch_begin;
+
+    for (int ch = ch_begin; ch <= ch_last; ++ch) {
+    const int p_lo = ch == ch_begin ? (int)(v_begin - (int64_t)ch * rpc) : 0;              // this block's parts of the chunk
+    const int p_hi = ch == ch_last ? (int)(v_end - (int64_t)ch * rpc) : rpc;
+    const ChunkDesc cd = ws.att_desc[ch];
+    int4 pgs = make_int4(0, 0, 0, 0);
+    if (PAGED) pgs = reinterpret_cast<const int4*>(ws.att_pages)[ch];   // the chunk's pages, beside its descriptor
+    const int seg = cd.seg;
+    if (seg != cur_seg) {                                         // (uniform over the block) a new segment: new queries, new state
+        if (cur_seg >= 0) {
+            flush(run_first);
+            reset();
+        }
+        cur_seg = seg;
+        run_first = p_lo == 0 ? ch : extra_base + (int)blockIdx.x;
+        // query fragments: lane (query c16, k-group b4), MFMA step j covers elements (4j + b4)*E ..
+        const int seq = seg / sh.segs_per_seq, lh = seg % sh.segs_per_seq;
+        const int layer = lh / sh.n_kv_heads, head = lh % sh.n_kv_heads;
+        const int64_t qrow = ((int64_t)seq * sh.n_layers + layer) * sh.n_q_heads + (int64_t)head * G + c16;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            qf[j] = c16 < G ? reinterpret_cast<const vec*>(q + qrow * D)[4 * j + b4] : F::zero();
+        t_now = SOFT ? now[seq] : 0;
+    }
+    const int row_end = cd.n;                                     // the chunk's rows are [0, n) counted from cd.first ...
+    const int off = p_lo * part_rows, row_stop = min(row_end, p_hi * part_rows);   // ... and this block's are [off, row_stop)
+    const int64_t base = cd.first;
 
     // PAGED: the (at most four) pages of the run come from the plan's table beside the descriptors, so no
     // load of the loop waits for a look-up in the block table
@@ -129,7 +206,7 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
         pg3 = np > 3 ? min(max(pgs.w, 0), hi) : 0;
     }
 
-    for (int r0 = off + wave * 16; r0 < row_end; r0 += 64) {
+    for (int r0 = off + wave * 16; r0 < row_stop; r0 += 64) {
         const int last = row_end - 1;
         int64_t rbase = base;                                     // entry of row 0 in this 16-row group's numbering
         if (PAGED) {                                              // 16 | page size: the group lies in one page
@@ -212,47 +289,8 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
         }
     }
 
-    // the wavefront's partial (the MFMAs have summed over its row groups already) goes to LDS, where the four
-    // wavefronts of the block are merged: s_o[wave][head][(4 i + b4) E + e] = column E (4 b4 + i) + e
-    float l_all = l;
-    l_all += __shfl_xor(l_all, 16, 64);
-    l_all += __shfl_xor(l_all, 32, 64);
-    if (c16 < G) {
-        if (b4 == 0) {
-            s_m[wave][c16] = m;
-            s_l[wave][c16] = l_all;
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            float* so = &s_o[wave][c16][(4 * i + b4) * E];
-#pragma unroll
-            for (int e4 = 0; e4 < E; e4 += 4)
-                *reinterpret_cast<float4*>(so + e4) = make_float4(o[e4][i], o[e4 + 1][i], o[e4 + 2][i], o[e4 + 3][i]);
-        }
-    }
-    __syncthreads();
-    float* part = ws.att_partial + (size_t)ch * G * (D + 2);
-    for (int idx = tid; idx < G * D; idx += ATT_THREADS) {
-        const int g = idx / D, d = idx % D;
-        const int cb = d / E;
-        const int so_at = (4 * (cb & 3) + (cb >> 2)) * E + d % E;
-        float M = -INFINITY;
-#pragma unroll
-        for (int s = 0; s < NSTREAM; ++s) M = fmaxf(M, s_m[s][g]);
-        const float Ms = M == -INFINITY ? 0.f : M;
-        float accd = 0.f, lsum = 0.f;
-#pragma unroll
-        for (int s = 0; s < NSTREAM; ++s) {
-            const float w = __builtin_amdgcn_exp2f(s_m[s][g] - Ms);
-            accd += s_o[s][g][so_at] * w;
-            lsum += s_l[s][g] * w;
-        }
-        part[g * (D + 2) + 2 + d] = accd;
-        if (d == 0) {
-            part[g * (D + 2)] = M;
-            part[g * (D + 2) + 1] = lsum;
-        }
-    }
+    }                                                             // (chunks of the block)
+    if (cur_seg >= 0) flush(run_first);
 }
 
 // One block per segment of the layer range: merges the partial results of its chunks, a tile
@@ -274,12 +312,16 @@ struct CombineExtra {
     const int32_t* kept;
 };
 
-template <int D, int EXTRA>
+// PERSIST: the partial results come from k_att_partial's fixed grid of persist_nb blocks - one per (block, segment)
+// run, at the slot of the run's first chunk or, for a run that starts inside a chunk, at slot extra_base + block -
+// and not one per chunk (the fused row mover's partials).
+template <int D, int EXTRA, bool PERSIST>
 __global__ __launch_bounds__(COMB_THREADS) void k_att_combine(Shape sh, Workspace ws,
                                                               const int32_t* __restrict__ chunk_prefix,
                                                               int layer_begin, int layer_end,
                                                               float* __restrict__ out, float* __restrict__ lse,
-                                                              CombineExtra ex) {
+                                                              CombineExtra ex, int persist_nb, int rpc,
+                                                              int extra_base) {
     __shared__ float s_m[COMB_TILE][8], s_w[COMB_TILE][8], s_l[COMB_TILE][8];
     __shared__ float s_M[8], s_a[8], s_L[8];
     const int G = sh.group;
@@ -309,11 +351,37 @@ __global__ __launch_bounds__(COMB_THREADS) void k_att_combine(Shape sh, Workspac
         s_L[tid] = 0.f;
     }
     const size_t stride = (size_t)G * (D + 2);
-    for (int t0 = c0; t0 < c1; t0 += COMB_TILE) {
-        const int nt = min(COMB_TILE, c1 - t0);
+    // entries to merge: entry e sits at slot_of(e).  PERSIST: block b of the attention kernel walked the parts
+    // [b V / nb, (b + 1) V / nb) of the table (rpc parts to a chunk, V = T rpc); the blocks that met this segment's parts
+    // [c0 rpc, c1 rpc) are b0 .. b1, and each left one partial result: at slot c0 if it came from an earlier segment, at
+    // the chunk it started with if it started with a whole chunk, else at its own extra slot.
+    int n = c1 - c0, b0 = 0, nb = 1;
+    int64_t V = 0;
+    if (PERSIST) {
+        const int64_t total = chunk_prefix[sh.nseg];
+        V = total * rpc;
+        nb = (int)min((int64_t)persist_nb, total);
+        if (c1 > c0) {
+            b0 = (int)((((int64_t)c0 * rpc + 1) * nb + V - 1) / V) - 1;          // the last block that starts at or before part c0 rpc
+            n = (int)(((int64_t)c1 * rpc * nb + V - 1) / V) - 1 - b0 + 1;        // ... up to the one that holds part c1 rpc - 1
+        } else {
+            n = 0;
+        }
+    }
+    __shared__ int s_slot[PERSIST ? COMB_TILE : 1];               // PERSIST: the slots of the tile's entries
+    auto slot_of = [&](int e) -> int {
+        if (!PERSIST) return c0 + e;
+        const int64_t vb = (int64_t)(b0 + e) * V / nb;
+        if (vb <= (int64_t)c0 * rpc) return c0;
+        return vb % rpc == 0 ? (int)(vb / rpc) : extra_base + b0 + e;
+    };
+    for (int t0 = 0; t0 < n; t0 += COMB_TILE) {
+        const int nt = min(COMB_TILE, n - t0);
         __syncthreads();
         for (int i = tid; i < nt * G; i += COMB_THREADS) {
-            const float* p = ws.att_partial + (size_t)(t0 + i / G) * stride + (size_t)(i % G) * (D + 2);
+            const int slot = slot_of(t0 + i / G);
+            if (PERSIST && i % G == 0) s_slot[i / G] = slot;
+            const float* p = ws.att_partial + (size_t)slot * stride + (size_t)(i % G) * (D + 2);
             s_m[i / G][i % G] = p[0];
             s_l[i / G][i % G] = p[1];
         }
@@ -341,17 +409,26 @@ __global__ __launch_bounds__(COMB_THREADS) void k_att_combine(Shape sh, Workspac
             const int idx = tid + p * COMB_THREADS;
             if (idx >= G * D) break;
             const int g = idx / D, d = idx % D;
-            const float* base = ws.att_partial + (size_t)t0 * stride + (size_t)g * (D + 2) + 2 + d;
+            const float* base = ws.att_partial + (size_t)g * (D + 2) + 2 + d;
             float av = acc[p] * s_a[g];
             int i = 0;
             for (; i + 8 <= nt; i += 8) {
                 float x[8];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) x[u] = base[(size_t)(i + u) * stride];
+                for (int u = 0; u < 8; ++u) x[u] = base[(size_t)(PERSIST ? s_slot[i + u] : c0 + t0 + i + u) * stride];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) av = fmaf(x[u], s_w[i + u][g], av);
             }
-            for (; i < nt; ++i) av = fmaf(base[(size_t)i * stride], s_w[i][g], av);
+            if (PERSIST) {                                        // (a handful of entries: all of them in flight at once)
+                float x[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) x[u] = base[(size_t)s_slot[min(i + u, nt - 1)] * stride];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (i + u < nt) av = fmaf(x[u], s_w[i + u][g], av);
+            } else {
+                for (; i < nt; ++i) av = fmaf(base[(size_t)(c0 + t0 + i) * stride], s_w[i][g], av);
+            }
             acc[p] = av;
         }
     }
@@ -370,25 +447,39 @@ __global__ __launch_bounds__(COMB_THREADS) void k_att_combine(Shape sh, Workspac
 template <int D, int G>
 static void launch_partial(const CacheView& c, const uint16_t* q, const Shape& sh, const Workspace& ws,
                            int chunk, float scale_log2, const int32_t* now, bool paged, unsigned blocks,
-                           hipStream_t st) {
+                           int rpc, int extra_base, hipStream_t st) {
     if (paged)
-        hipLaunchKernelGGL((k_att_partial<D, G, false, true>), dim3(blocks), dim3(ATT_THREADS), 0, st, c, q, sh, ws, chunk, scale_log2, now);
+        hipLaunchKernelGGL((k_att_partial<D, G, false, true>), dim3(blocks), dim3(ATT_THREADS), 0, st, c, q, sh, ws, chunk, scale_log2, now, rpc, extra_base);
     else if (now)
-        hipLaunchKernelGGL((k_att_partial<D, G, true, false>), dim3(blocks), dim3(ATT_THREADS), 0, st, c, q, sh, ws, chunk, scale_log2, now);
+        hipLaunchKernelGGL((k_att_partial<D, G, true, false>), dim3(blocks), dim3(ATT_THREADS), 0, st, c, q, sh, ws, chunk, scale_log2, now, rpc, extra_base);
     else
-        hipLaunchKernelGGL((k_att_partial<D, G, false, false>), dim3(blocks), dim3(ATT_THREADS), 0, st, c, q, sh, ws, chunk, scale_log2, now);
+        hipLaunchKernelGGL((k_att_partial<D, G, false, false>), dim3(blocks), dim3(ATT_THREADS), 0, st, c, q, sh, ws, chunk, scale_log2, now, rpc, extra_base);
 }
 
 template <int D>
 static bool dispatch_partial(int G, const CacheView& c, const uint16_t* q, const Shape& sh, const Workspace& ws,
                              int chunk, float scale_log2, const int32_t* now, bool paged, unsigned blocks,
-                             hipStream_t st) {
+                             int rpc, int extra_base, hipStream_t st) {
     switch (G) {
-#define KVTRIM_CASE(g) case g: launch_partial<D, g>(c, q, sh, ws, chunk, scale_log2, now, paged, blocks, st); return true;
+#define KVTRIM_CASE(g) case g: launch_partial<D, g>(c, q, sh, ws, chunk, scale_log2, now, paged, blocks, rpc, extra_base, st); return true;
         KVTRIM_CASE(1) KVTRIM_CASE(2) KVTRIM_CASE(3) KVTRIM_CASE(4) KVTRIM_CASE(5) KVTRIM_CASE(6) KVTRIM_CASE(7) KVTRIM_CASE(8)
 #undef KVTRIM_CASE
         default: return false;
     }
+}
+
+// The fixed grid of k_att_partial for a table of at most max_chunks chunks of `chunk` rows: nb blocks; every chunk
+// counts as rpc parts of 64 rows when the partial-result buffer has nb slots to spare behind the chunks' own (for the
+// runs that start inside a chunk), else the blocks' shares are whole chunks.
+struct AttGrid {
+    int nb, rpc, extra_base;
+};
+static AttGrid att_grid(const kvtrim_ctx* ctx, int64_t max_chunks, int chunk) {
+    AttGrid g;
+    g.nb = (int)(max_chunks < ctx->att_blocks ? max_chunks : ctx->att_blocks);
+    g.extra_base = (int)max_chunks;
+    g.rpc = max_chunks + g.nb <= ctx->ws.max_att_chunks && chunk % 64 == 0 ? chunk / 64 : 1;
+    return g;
 }
 
 int att_chunk_for(const kvtrim_ctx* ctx, int64_t cap) {
@@ -403,6 +494,8 @@ kvtrim_status launch_attn(kvtrim_ctx* ctx, const CacheView& c, const uint16_t* q
     const Workspace& ws = ctx->ws;
     const int chunk = att_chunk_for(ctx, c.cap);
     const int64_t max_chunks = c.cap / chunk + sh.nseg;
+    const AttGrid ag = att_grid(ctx, max_chunks, chunk);
+    const int nb = ag.nb;
     const float scale_log2 = scale * 1.4426950408889634f;
     { ProfScope prof(ctx, K_ATT_PLAN, st);
       hipLaunchKernelGGL(k_att_plan, dim3(1), dim3(1024), 0, st, c, sh, ws, chunk, layer_begin, layer_end, max_chunks); }
@@ -410,11 +503,11 @@ kvtrim_status launch_attn(kvtrim_ctx* ctx, const CacheView& c, const uint16_t* q
     {
         ProfScope prof(ctx, K_ATT_PARTIAL, st);
         ok = sh.head_dim == 128
-                  ? dispatch_partial<128>(sh.group, c, q, sh, ws, chunk, scale_log2, soft_now, false, (unsigned)max_chunks, st)
-                  : dispatch_partial<64>(sh.group, c, q, sh, ws, chunk, scale_log2, soft_now, false, (unsigned)max_chunks, st);
+                  ? dispatch_partial<128>(sh.group, c, q, sh, ws, chunk, scale_log2, soft_now, false, (unsigned)nb, ag.rpc, ag.extra_base, st)
+                  : dispatch_partial<64>(sh.group, c, q, sh, ws, chunk, scale_log2, soft_now, false, (unsigned)nb, ag.rpc, ag.extra_base, st);
     }
     if (!ok) return KVTRIM_EINVAL;
-    return launch_combine(ctx, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, st);
+    return launch_combine(ctx, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, st, nb, ag.rpc, ag.extra_base);
 }
 
 // Attention over the page runs listed in ws.att_desc / ws.att_chunk_prefix (built by the paged plan
@@ -426,25 +519,28 @@ kvtrim_status launch_attn_paged(kvtrim_ctx* ctx, const CacheView& pool, const in
     const Shape& sh = ctx->shape;
     Workspace ws = ctx->ws;
     ws.pg_block_table = block_table;
+    constexpr int chunk = ATT_PAGE_GROUP * KVTRIM_PAGE_SIZE;
+    const AttGrid ag = att_grid(ctx, max_chunks, chunk);
+    const int nb = ag.nb;
     const float scale_log2 = scale * 1.4426950408889634f;
     bool ok;
     {
         ProfScope prof(ctx, K_ATT_PARTIAL, st);
         ok = sh.head_dim == 128
-                 ? dispatch_partial<128>(sh.group, pool, q, sh, ws, KVTRIM_PAGE_SIZE, scale_log2, nullptr, true, (unsigned)max_chunks, st)
-                 : dispatch_partial<64>(sh.group, pool, q, sh, ws, KVTRIM_PAGE_SIZE, scale_log2, nullptr, true, (unsigned)max_chunks, st);
+                 ? dispatch_partial<128>(sh.group, pool, q, sh, ws, chunk, scale_log2, nullptr, true, (unsigned)nb, ag.rpc, ag.extra_base, st)
+                 : dispatch_partial<64>(sh.group, pool, q, sh, ws, chunk, scale_log2, nullptr, true, (unsigned)nb, ag.rpc, ag.extra_base, st);
     }
     if (!ok) return KVTRIM_EINVAL;
-    if (!tidy) return launch_combine(ctx, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, st);
+    if (!tidy) return launch_combine(ctx, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, st, nb, ag.rpc, ag.extra_base);
     // the merge, and in the same launch one block per segment that tidies its block table
     CombineExtra ex{};
     ex.tidy = *tidy;
     const unsigned nblk = (unsigned)(sh.n_seq * (layer_end - layer_begin) * sh.n_kv_heads + sh.nseg);
     ProfScope prof(ctx, K_ATT_COMBINE, st);
     if (sh.head_dim == 128)
-        hipLaunchKernelGGL((k_att_combine<128, EXTRA_TIDY>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, ex);
+        hipLaunchKernelGGL((k_att_combine<128, EXTRA_TIDY, true>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, ex, nb, ag.rpc, ag.extra_base);
     else
-        hipLaunchKernelGGL((k_att_combine<64, EXTRA_TIDY>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, ex);
+        hipLaunchKernelGGL((k_att_combine<64, EXTRA_TIDY, true>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, ex, nb, ag.rpc, ag.extra_base);
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;
 }
@@ -452,15 +548,21 @@ kvtrim_status launch_attn_paged(kvtrim_ctx* ctx, const CacheView& pool, const in
 // Merges the per-chunk partial results in ws.att_partial; chunk_prefix[g] .. chunk_prefix[g+1]
 // are the chunks of segment g.
 kvtrim_status launch_combine(kvtrim_ctx* ctx, const int32_t* chunk_prefix, int32_t layer_begin,
-                             int32_t layer_end, float* out, float* lse, hipStream_t st) {
+                             int32_t layer_end, float* out, float* lse, hipStream_t st, int persist_nb, int rpc,
+                             int extra_base) {
     const Shape& sh = ctx->shape;
     const Workspace& ws = ctx->ws;
     const unsigned nblk = (unsigned)(sh.n_seq * (layer_end - layer_begin) * sh.n_kv_heads);
     ProfScope prof(ctx, K_ATT_COMBINE, st);
-    if (sh.head_dim == 128)
-        hipLaunchKernelGGL((k_att_combine<128, EXTRA_NONE>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse, CombineExtra{});
+    if (persist_nb > 0) {
+        if (sh.head_dim == 128)
+            hipLaunchKernelGGL((k_att_combine<128, EXTRA_NONE, true>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse, CombineExtra{}, persist_nb, rpc, extra_base);
+        else
+            hipLaunchKernelGGL((k_att_combine<64, EXTRA_NONE, true>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse, CombineExtra{}, persist_nb, rpc, extra_base);
+    } else if (sh.head_dim == 128)
+        hipLaunchKernelGGL((k_att_combine<128, EXTRA_NONE, false>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse, CombineExtra{}, 0, 1, 0);
     else
-        hipLaunchKernelGGL((k_att_combine<64, EXTRA_NONE>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse, CombineExtra{});
+        hipLaunchKernelGGL((k_att_combine<64, EXTRA_NONE, false>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse, CombineExtra{}, 0, 1, 0);
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;
 }
@@ -480,9 +582,9 @@ kvtrim_status launch_combine_unstage(kvtrim_ctx* ctx, const int32_t* chunk_prefi
     const unsigned nblk = (unsigned)(sh.n_seq * (layer_end - layer_begin) * sh.n_kv_heads + (max_chunks + per_block - 1) / per_block);
     ProfScope prof(ctx, K_ATT_COMBINE, st);
     if (sh.head_dim == 128)
-        hipLaunchKernelGGL((k_att_combine<128, EXTRA_UNSTAGE>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse, ex);
+        hipLaunchKernelGGL((k_att_combine<128, EXTRA_UNSTAGE, false>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse, ex, 0, 1, 0);
     else
-        hipLaunchKernelGGL((k_att_combine<64, EXTRA_UNSTAGE>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse, ex);
+        hipLaunchKernelGGL((k_att_combine<64, EXTRA_UNSTAGE, false>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse, ex, 0, 1, 0);
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;
 }

@@ -246,6 +246,11 @@ kvtrim_status kvtrim_create(kvtrim_ctx** out, const kvtrim_config* cfg) {
         const int v = atoi(e);
         if (v >= 256 && v <= 65536 && v % 64 == 0) ctx->att_chunk_min = v;
     }
+    ctx->att_blocks = 768;                                        // three blocks of k_att_partial per compute unit
+    if (const char* e = getenv("KVTRIM_ATT_BLOCKS")) {           // tuning knob
+        const int v = atoi(e);
+        if (v >= 1 && v <= 65536) ctx->att_blocks = v;
+    }
     const Layout l = layout_of(cfg, false);
     ctx->ws_bytes = l.total;
     hipError_t e = hipGetDevice(&ctx->device);

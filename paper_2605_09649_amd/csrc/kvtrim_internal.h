@@ -222,6 +222,7 @@ struct kvtrim_ctx {
     int32_t* err_host;           // pinned mirror of the device flag
     int device;
     int att_chunk_min;           // rows per attention chunk (multiple of 64, >= 256); KVTRIM_ATT_CHUNK overrides
+    int att_blocks;              // blocks of the attention kernel's fixed grid; KVTRIM_ATT_BLOCKS overrides
     char last_error[256];
     // instrumentation
     uint64_t prof_mask;
@@ -292,8 +293,10 @@ kvtrim_status launch_cmp_copy(kvtrim_ctx*, const CacheView& src, const uint8_t* 
 kvtrim_status launch_occupancy(kvtrim_ctx*, const CacheView&, const int32_t* now, double* occ, hipStream_t);
 void launch_cmp_scan(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const int32_t* kept,
                      const CacheViewMut& dst, int32_t reserve, hipStream_t);
+// persist_nb > 0: the partial results are those of k_att_partial launched with that many blocks (one per block and
+// segment; rpc parts to a chunk, extra slots from extra_base on)
 kvtrim_status launch_combine(kvtrim_ctx*, const int32_t* chunk_prefix, int32_t layer_begin, int32_t layer_end,
-                             float* out, float* lse, hipStream_t);
+                             float* out, float* lse, hipStream_t, int persist_nb = 0, int rpc = 1, int extra_base = 0);
 // ... whose launch also finishes an in-place compaction: the rows parked in `stage` go to their places
 kvtrim_status launch_combine_unstage(kvtrim_ctx*, const int32_t* chunk_prefix, int32_t layer_begin, int32_t layer_end,
                                      float* out, float* lse, const CacheViewMut& c, const CacheViewMut& stage,
