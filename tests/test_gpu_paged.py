@@ -59,6 +59,19 @@ def test_ragged_segments_with_empty_ones_paged(S, L, H, G, D):
     check(run_paged_both(w, [budget] * 4, device=DEV, cache_dict=c, now0=now.numpy()))
 
 
+@pytest.mark.parametrize("blocks", [1, 3, 10, 100000])
+def test_paged_attention_for_any_size_of_the_fixed_grid(blocks, monkeypatch):
+    # as in the ragged path: whatever the number of blocks of the attention kernel, the merge finds their partial results
+    monkeypatch.setenv("KVTRIM_ATT_BLOCKS", str(blocks))
+    w = wl(1, 2, 3, 2, 64)
+    seg_len = [2900, 130, 0, 1024, 255, 3000]
+    c, now = ki.ragged_cache(w, seg_len, reserve=1, salt=12)
+    total = sum(seg_len)
+    check(run_paged_both(w, [[total - 100], [total - 300], [total - 301]], device=DEV, cache_dict=c, now0=now.numpy()))
+    check(run_paged_both(w, [[total - 100], [total - 300], [total - 301]], device=DEV, cache_dict=c, now0=now.numpy(), hint=60,
+                         one_call=True))
+
+
 def test_pages_are_freed_and_taken_again():
     # the budget shrinks (pages empty out and return to the free list), then grows past the cache
     # size (nothing is evicted, every full segment takes a page from the free list)

@@ -461,6 +461,34 @@ def test_attention_against_oracle_and_layer_ranges(D, G):
     assert np.array_equal(o2[:, 1], o[:, 1])
 
 
+@pytest.mark.parametrize("blocks", [1, 2, 3, 7, 50, 100000])
+def test_attention_for_any_size_of_the_fixed_grid(blocks, monkeypatch):
+    # the attention kernel's blocks share the chunk table in equal parts of 64 rows and leave one partial result per
+    # block and segment; whatever the number of blocks (a tuning knob read when the context is created) - one block
+    # that walks everything, shares that end inside a chunk or inside a segment, more blocks than chunks - the
+    # merge must find exactly those partial results
+    monkeypatch.setenv("KVTRIM_ATT_BLOCKS", str(blocks))
+    w = wl(2, 2, 2, 4, 128)
+    seg_len = [3000, 0, 513, 64, 1, 2049, 700, 5000]
+    c, _ = ki.ragged_cache(w, seg_len, salt=21)
+    hc = host_cache(w, c)
+    dc = kv.Cache.from_dict(c, DEV)
+    ctx = kv.Context(w.n_seq, w.n_layers, w.n_kv_heads, w.n_q_heads, 128, hc.cap)
+    q = ki.decode_inputs(w, 0)["q"]
+    scale = 1.0 / math.sqrt(128)
+    ref, ref_lse = oracle.attend(hc, bf16_bits(q), scale)
+    for rng in ((0, 2), (1, 2)):
+        out = torch.full(ref.shape, 99.0, dtype=torch.float32, device=DEV)
+        lse = torch.full(ref_lse.shape, 99.0, dtype=torch.float32, device=DEV)
+        kv.kvtrim_decode_attn(ctx, dc, q.to(DEV), rng[0], rng[1], scale, out, lse)
+        assert kv.kvtrim_poll_error(ctx) == 0
+        o, l = out.cpu().numpy()[:, rng[0]:rng[1]], lse.cpu().numpy()[:, rng[0]:rng[1]]
+        assert attn_error(o, ref[:, rng[0]:rng[1]]) <= ATTN_TOL, (blocks, rng)
+        fin = np.isfinite(ref_lse[:, rng[0]:rng[1]])
+        assert np.abs(l[fin] - ref_lse[:, rng[0]:rng[1]][fin]).max() <= 2e-3
+        assert np.array_equal(np.isneginf(l), ~fin)
+
+
 def test_attention_with_large_logits_stays_finite():
     w = wl(1, 1, 1, 4, 128)
     c, _ = ki.ragged_cache(w, [900], salt=10)
