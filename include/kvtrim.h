@@ -186,7 +186,10 @@ kvtrim_status kvtrim_compact(kvtrim_ctx *ctx, const kvtrim_cache *src, const uin
  * q: device bf16 [n_seq][n_layers][n_q_heads][head_dim].
  * out: device fp32, same shape; lse: optional (may be NULL) device fp32
  * [n_seq][n_layers][n_q_heads] = log sum_i exp(z_i).  An empty segment gives
- * out = 0 and lse = -inf.  Heads of layers outside the range are not written. */
+ * out = 0 and lse = -inf.  Heads of layers outside the range are not written.
+ * The same call on the same cache gives the same bits; the order of the fp32 sums depends
+ * on how the call's rows are shared out among the kernel's blocks, so two calls with
+ * different layer ranges (or caches of different sizes) may differ in the last bits. */
 kvtrim_status kvtrim_decode_attn(kvtrim_ctx *ctx, const kvtrim_cache *c, const void *q,
                                  int32_t layer_begin, int32_t layer_end, float softmax_scale,
                                  float *out, float *lse, void *hip_stream);

@@ -36,7 +36,7 @@ __global__ __launch_bounds__(1024) void k_att_plan(CacheView c, Shape sh, Worksp
         return layer >= layer_begin && layer < layer_end;
     };
     build_chunk_table(c.seg_len, c.seg_start, sh.nseg, in_range, chunk, c.cap, ws.att_chunk_prefix,
-                      ws.att_desc, max_chunks, nullptr, ws.err);
+                      ws.att_desc, max_chunks, ws.att_row_prefix, ws.err);
 }
 
 template <int D>
@@ -80,7 +80,7 @@ template <int D, int G, bool SOFT, bool PAGED>
 __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const uint16_t* __restrict__ q,
                                                              Shape sh, Workspace ws, int chunk,
                                                              float scale_log2, const int32_t* __restrict__ now,
-                                                             int rpc, int extra_base) {
+                                                             int round_rows, int extra_base) {
     typedef Frag<D> F;
     typedef typename F::vec vec;
     constexpr int E = F::E;
@@ -90,21 +90,40 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
     __shared__ __attribute__((aligned(16))) float s_o[NSTREAM][G][SO];
 
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
-    // The grid is fixed (a few blocks per compute unit).  Every chunk of the table (T chunks of `chunk` rows, ragged
-    // ones at the segments' ends) counts as rpc parts of chunk / rpc rows; block b walks the parts [b V / nb, (b + 1) V / nb),
-    // V = T rpc, so the blocks' shares differ by one part at most, and keeps ONE online-softmax state for as long as
-    // its parts belong to the same segment: a partial result is written per (block, segment) run and not per chunk -
-    // at the slot of the run's first chunk, or at slot extra_base + b when the run starts inside a chunk (which only a
-    // block's first chunk can do; the block before it owns that chunk's slot).
+    // The grid is fixed (a few blocks per compute unit).  The rows of the layer range's segments, one segment after the
+    // other (ws.att_row_prefix; N rows in all), are shared out equally: block b starts at the row b N / nb, rounded down
+    // to a multiple of round_rows inside its segment (64: a round of the four wavefronts; a whole chunk when the
+    // partial-result buffer has no extra slots to spare), and ends where block b + 1 starts.  A
+    // block keeps ONE online-softmax state for as long as its rows belong to the same segment: a partial result is
+    // written per (block, segment) run and not per chunk - at the slot of the chunk that the run starts with, or at
+    // slot extra_base + b when the run starts inside a chunk (the block before it owns that chunk's slot).
     // On this GPU a stream of reads slows down by far more than the bytes suggest when result writes are mixed into
     // it (8.5 MB of writes in a 1.1 GB read stream cost 12 us of 170), so the fewer partial results the better.
     const int total = ws.att_chunk_prefix[sh.nseg];
     const int nb = min((int)gridDim.x, total);
     if ((int)blockIdx.x >= nb) return;
-    const int64_t V = (int64_t)total * rpc;
-    const int64_t v_begin = (int64_t)blockIdx.x * V / nb, v_end = (int64_t)(blockIdx.x + 1) * V / nb;   // (at least rpc parts)
-    const int ch_begin = (int)(v_begin / rpc), ch_last = (int)((v_end - 1) / rpc);
-    const int part_rows = chunk / rpc;
+    const int64_t* rp = ws.att_row_prefix;
+    const int64_t N = rp[sh.nseg];
+    // where row e of the concatenation lies: the segment s with rp[s] <= e < rp[s + 1], and the round of 64 rows inside it
+    auto locate = [&](int64_t e, int& seg_at, int& row_at) {
+        if (e >= N) {
+            seg_at = sh.nseg;
+            row_at = 0;
+            return;
+        }
+        int lo = 0, hi = sh.nseg;                                 // invariant: rp[lo] <= e < rp[hi]
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (rp[mid] <= e) lo = mid;
+            else hi = mid;
+        }
+        seg_at = lo;
+        row_at = (int)(e - rp[lo]) / round_rows * round_rows;
+    };
+    int seg_b, row_b, seg_e, row_e;
+    locate((int64_t)blockIdx.x * N / nb, seg_b, row_b);
+    locate((int64_t)(blockIdx.x + 1) * N / nb, seg_e, row_e);
+    if (seg_b == seg_e && row_b == row_e) return;                 // (shares of less than a round: a later block has the rows)
     const int c16 = lane & 15, b4 = lane >> 4;
     const vec* kp = reinterpret_cast<const vec*>(c.k);
     const vec* vp = reinterpret_cast<const vec*>(c.v);
@@ -165,24 +184,14 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
         }
         __syncthreads();                                          // (the next run's partials may overwrite LDS)
     };
+    for (int seg = seg_b; seg <= seg_e && seg < sh.nseg; ++seg) {
+    const int c0 = ws.att_chunk_prefix[seg], c1 = ws.att_chunk_prefix[seg + 1];
+    const int run_lo = seg == seg_b ? row_b : 0;                  // this block's rows of the segment: [run_lo, run_hi)
+    const int run_hi = seg == seg_e ? row_e : (int)(rp[seg + 1] - rp[seg]);
+    if (c0 >= c1 || run_lo >= run_hi) continue;                   // (uniform over the block)
+    const int run_slot = run_lo % chunk == 0 ? c0 + run_lo / chunk : extra_base + (int)blockIdx.x;
     reset();
-    int cur_seg = -1, run_first = ch_begin;
-
-    for (int ch = ch_begin; ch <= ch_last; ++ch) {
-    const int p_lo = ch == ch_begin ? (int)(v_begin - (int64_t)ch * rpc) : 0;              // this block's parts of the chunk
-    const int p_hi = ch == ch_last ? (int)(v_end - (int64_t)ch * rpc) : rpc;
-    const ChunkDesc cd = ws.att_desc[ch];
-    int4 pgs = make_int4(0, 0, 0, 0);
-    if (PAGED) pgs = reinterpret_cast<const int4*>(ws.att_pages)[ch];   // the chunk's pages, beside its descriptor
-    const int seg = cd.seg;
-    if (seg != cur_seg) {                                         // (uniform over the block) a new segment: new queries, new state
-        if (cur_seg >= 0) {
-            flush(run_first);
-            reset();
-        }
-        cur_seg = seg;
-        run_first = p_lo == 0 ? ch : extra_base + (int)blockIdx.x;
-        // query fragments: lane (query c16, k-group b4), MFMA step j covers elements (4j + b4)*E ..
+    {   // query fragments: lane (query c16, k-group b4), MFMA step j covers elements (4j + b4)*E ..
         const int seq = seg / sh.segs_per_seq, lh = seg % sh.segs_per_seq;
         const int layer = lh / sh.n_kv_heads, head = lh % sh.n_kv_heads;
         const int64_t qrow = ((int64_t)seq * sh.n_layers + layer) * sh.n_q_heads + (int64_t)head * G + c16;
@@ -191,8 +200,14 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
             qf[j] = c16 < G ? reinterpret_cast<const vec*>(q + qrow * D)[4 * j + b4] : F::zero();
         t_now = SOFT ? now[seq] : 0;
     }
+    const int ch_first = c0 + run_lo / chunk, ch_last = min(c1 - 1, c0 + (run_hi - 1) / chunk);
+    for (int ch = ch_first; ch <= ch_last; ++ch) {
+    const ChunkDesc cd = ws.att_desc[ch];
+    int4 pgs = make_int4(0, 0, 0, 0);
+    if (PAGED) pgs = reinterpret_cast<const int4*>(ws.att_pages)[ch];   // the chunk's pages, beside its descriptor
+    const int ch_row0 = (ch - c0) * chunk;                        // the chunk's first row in the segment's numbering
     const int row_end = cd.n;                                     // the chunk's rows are [0, n) counted from cd.first ...
-    const int off = p_lo * part_rows, row_stop = min(row_end, p_hi * part_rows);   // ... and this block's are [off, row_stop)
+    const int off = max(run_lo - ch_row0, 0), row_stop = min(row_end, run_hi - ch_row0);   // ... and this block's are [off, row_stop)
     const int64_t base = cd.first;
 
     // PAGED: the (at most four) pages of the run come from the plan's table beside the descriptors, so no
@@ -289,8 +304,9 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
         }
     }
 
-    }                                                             // (chunks of the block)
-    if (cur_seg >= 0) flush(run_first);
+    }                                                             // (chunks of the run)
+    flush(run_slot);
+    }                                                             // (segments of the block)
 }
 
 // One block per segment of the layer range: merges the partial results of its chunks, a tile
@@ -320,8 +336,8 @@ __global__ __launch_bounds__(COMB_THREADS) void k_att_combine(Shape sh, Workspac
                                                               const int32_t* __restrict__ chunk_prefix,
                                                               int layer_begin, int layer_end,
                                                               float* __restrict__ out, float* __restrict__ lse,
-                                                              CombineExtra ex, int persist_nb, int rpc,
-                                                              int extra_base) {
+                                                              CombineExtra ex, int persist_nb, int round_rows,
+                                                              int chunk_rows, int extra_base) {
     __shared__ float s_m[COMB_TILE][8], s_w[COMB_TILE][8], s_l[COMB_TILE][8];
     __shared__ float s_M[8], s_a[8], s_L[8];
     const int G = sh.group;
@@ -351,39 +367,47 @@ __global__ __launch_bounds__(COMB_THREADS) void k_att_combine(Shape sh, Workspac
         s_L[tid] = 0.f;
     }
     const size_t stride = (size_t)G * (D + 2);
-    // entries to merge: entry e sits at slot_of(e).  PERSIST: block b of the attention kernel walked the parts
-    // [b V / nb, (b + 1) V / nb) of the table (rpc parts to a chunk, V = T rpc); the blocks that met this segment's parts
-    // [c0 rpc, c1 rpc) are b0 .. b1, and each left one partial result: at slot c0 if it came from an earlier segment, at
-    // the chunk it started with if it started with a whole chunk, else at its own extra slot.
+    // entries to merge: entry e sits at slot_of(e).  PERSIST: block b of the attention kernel started at row b N / nb of
+    // the concatenated segments (ws.att_row_prefix), rounded down to a multiple of round_rows inside its segment, and
+    // ended where block b + 1 started.  The blocks that had rows of this segment are b0 - the last one that starts at
+    // or before the segment's first row - up to b1, the last one that starts inside it; each left one partial result:
+    // b0 at slot c0, a later one at the slot of the chunk it started with or, if it started inside a chunk, at its own
+    // extra slot.  (A block whose start and end round to the same row had nothing to do: weight zero.)
     int n = c1 - c0, b0 = 0, nb = 1;
-    int64_t V = 0;
+    int64_t N = 0, r0s = 0, r1s = 0;                              // rows of all segments / before this one / up to its end
     if (PERSIST) {
         const int64_t total = chunk_prefix[sh.nseg];
-        V = total * rpc;
+        N = ws.att_row_prefix[sh.nseg];
+        r0s = ws.att_row_prefix[seg];
+        r1s = ws.att_row_prefix[seg + 1];
         nb = (int)min((int64_t)persist_nb, total);
-        if (c1 > c0) {
-            b0 = (int)((((int64_t)c0 * rpc + 1) * nb + V - 1) / V) - 1;          // the last block that starts at or before part c0 rpc
-            n = (int)(((int64_t)c1 * rpc * nb + V - 1) / V) - 1 - b0 + 1;        // ... up to the one that holds part c1 rpc - 1
+        if (c1 > c0 && r1s > r0s) {
+            const int64_t lim0 = min(r0s + round_rows, r1s);      // starts below this row round down to the segment's first
+            b0 = (int)((lim0 * nb + N - 1) / N) - 1;
+            n = (int)((r1s * nb + N - 1) / N) - 1 - b0 + 1;
         } else {
             n = 0;
         }
     }
-    __shared__ int s_slot[PERSIST ? COMB_TILE : 1];               // PERSIST: the slots of the tile's entries
+    __shared__ int s_slot[PERSIST ? COMB_TILE : 1];               // PERSIST: the slots of the tile's entries (-1: nothing there)
     auto slot_of = [&](int e) -> int {
         if (!PERSIST) return c0 + e;
-        const int64_t vb = (int64_t)(b0 + e) * V / nb;
-        if (vb <= (int64_t)c0 * rpc) return c0;
-        return vb % rpc == 0 ? (int)(vb / rpc) : extra_base + b0 + e;
+        if (e == 0) return c0;
+        const int b = b0 + e;
+        const int64_t eb = (int64_t)b * N / nb, en = (int64_t)(b + 1) * N / nb;
+        const int row = (int)(eb - r0s) / round_rows * round_rows;
+        if (en < r1s && (int)(en - r0s) / round_rows * round_rows == row) return -1;   // an empty share
+        return row % chunk_rows == 0 ? c0 + row / chunk_rows : extra_base + b;
     };
     for (int t0 = 0; t0 < n; t0 += COMB_TILE) {
         const int nt = min(COMB_TILE, n - t0);
         __syncthreads();
         for (int i = tid; i < nt * G; i += COMB_THREADS) {
             const int slot = slot_of(t0 + i / G);
-            if (PERSIST && i % G == 0) s_slot[i / G] = slot;
-            const float* p = ws.att_partial + (size_t)slot * stride + (size_t)(i % G) * (D + 2);
-            s_m[i / G][i % G] = p[0];
-            s_l[i / G][i % G] = p[1];
+            if (PERSIST && i % G == 0) s_slot[i / G] = max(slot, c0);           // (an empty share: any slot, with weight zero)
+            const float* p = ws.att_partial + (size_t)max(slot, c0) * stride + (size_t)(i % G) * (D + 2);
+            s_m[i / G][i % G] = slot < 0 ? -INFINITY : p[0];
+            s_l[i / G][i % G] = slot < 0 ? 0.f : p[1];
         }
         __syncthreads();
         if (tid < G) {                                            // running maximum and rescale factor per query head
@@ -447,38 +471,39 @@ __global__ __launch_bounds__(COMB_THREADS) void k_att_combine(Shape sh, Workspac
 template <int D, int G>
 static void launch_partial(const CacheView& c, const uint16_t* q, const Shape& sh, const Workspace& ws,
                            int chunk, float scale_log2, const int32_t* now, bool paged, unsigned blocks,
-                           int rpc, int extra_base, hipStream_t st) {
+                           int round_rows, int extra_base, hipStream_t st) {
     if (paged)
-        hipLaunchKernelGGL((k_att_partial<D, G, false, true>), dim3(blocks), dim3(ATT_THREADS), 0, st, c, q, sh, ws, chunk, scale_log2, now, rpc, extra_base);
+        hipLaunchKernelGGL((k_att_partial<D, G, false, true>), dim3(blocks), dim3(ATT_THREADS), 0, st, c, q, sh, ws, chunk, scale_log2, now, round_rows, extra_base);
     else if (now)
-        hipLaunchKernelGGL((k_att_partial<D, G, true, false>), dim3(blocks), dim3(ATT_THREADS), 0, st, c, q, sh, ws, chunk, scale_log2, now, rpc, extra_base);
+        hipLaunchKernelGGL((k_att_partial<D, G, true, false>), dim3(blocks), dim3(ATT_THREADS), 0, st, c, q, sh, ws, chunk, scale_log2, now, round_rows, extra_base);
     else
-        hipLaunchKernelGGL((k_att_partial<D, G, false, false>), dim3(blocks), dim3(ATT_THREADS), 0, st, c, q, sh, ws, chunk, scale_log2, now, rpc, extra_base);
+        hipLaunchKernelGGL((k_att_partial<D, G, false, false>), dim3(blocks), dim3(ATT_THREADS), 0, st, c, q, sh, ws, chunk, scale_log2, now, round_rows, extra_base);
 }
 
 template <int D>
 static bool dispatch_partial(int G, const CacheView& c, const uint16_t* q, const Shape& sh, const Workspace& ws,
                              int chunk, float scale_log2, const int32_t* now, bool paged, unsigned blocks,
-                             int rpc, int extra_base, hipStream_t st) {
+                             int round_rows, int extra_base, hipStream_t st) {
     switch (G) {
-#define KVTRIM_CASE(g) case g: launch_partial<D, g>(c, q, sh, ws, chunk, scale_log2, now, paged, blocks, rpc, extra_base, st); return true;
+#define KVTRIM_CASE(g) case g: launch_partial<D, g>(c, q, sh, ws, chunk, scale_log2, now, paged, blocks, round_rows, extra_base, st); return true;
         KVTRIM_CASE(1) KVTRIM_CASE(2) KVTRIM_CASE(3) KVTRIM_CASE(4) KVTRIM_CASE(5) KVTRIM_CASE(6) KVTRIM_CASE(7) KVTRIM_CASE(8)
 #undef KVTRIM_CASE
         default: return false;
     }
 }
 
-// The fixed grid of k_att_partial for a table of at most max_chunks chunks of `chunk` rows: nb blocks; every chunk
-// counts as rpc parts of 64 rows when the partial-result buffer has nb slots to spare behind the chunks' own (for the
-// runs that start inside a chunk), else the blocks' shares are whole chunks.
+// The fixed grid of k_att_partial for a table of at most max_chunks chunks of `chunk` rows: nb blocks, whose shares
+// start at multiples of 64 rows when the partial-result buffer has nb slots to spare behind the chunks' own (for the
+// runs that start inside a chunk), else at whole chunks.
 struct AttGrid {
-    int nb, rpc, extra_base;
+    int nb, round_rows, chunk_rows, extra_base;
 };
 static AttGrid att_grid(const kvtrim_ctx* ctx, int64_t max_chunks, int chunk) {
     AttGrid g;
     g.nb = (int)(max_chunks < ctx->att_blocks ? max_chunks : ctx->att_blocks);
     g.extra_base = (int)max_chunks;
-    g.rpc = max_chunks + g.nb <= ctx->ws.max_att_chunks && chunk % 64 == 0 ? chunk / 64 : 1;
+    g.chunk_rows = chunk;
+    g.round_rows = max_chunks + g.nb <= ctx->ws.max_att_chunks && chunk % 64 == 0 ? 64 : chunk;
     return g;
 }
 
@@ -503,11 +528,11 @@ kvtrim_status launch_attn(kvtrim_ctx* ctx, const CacheView& c, const uint16_t* q
     {
         ProfScope prof(ctx, K_ATT_PARTIAL, st);
         ok = sh.head_dim == 128
-                  ? dispatch_partial<128>(sh.group, c, q, sh, ws, chunk, scale_log2, soft_now, false, (unsigned)nb, ag.rpc, ag.extra_base, st)
-                  : dispatch_partial<64>(sh.group, c, q, sh, ws, chunk, scale_log2, soft_now, false, (unsigned)nb, ag.rpc, ag.extra_base, st);
+                  ? dispatch_partial<128>(sh.group, c, q, sh, ws, chunk, scale_log2, soft_now, false, (unsigned)nb, ag.round_rows, ag.extra_base, st)
+                  : dispatch_partial<64>(sh.group, c, q, sh, ws, chunk, scale_log2, soft_now, false, (unsigned)nb, ag.round_rows, ag.extra_base, st);
     }
     if (!ok) return KVTRIM_EINVAL;
-    return launch_combine(ctx, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, st, nb, ag.rpc, ag.extra_base);
+    return launch_combine(ctx, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, st, nb, ag.round_rows, ag.chunk_rows, ag.extra_base);
 }
 
 // Attention over the page runs listed in ws.att_desc / ws.att_chunk_prefix (built by the paged plan
@@ -527,20 +552,20 @@ kvtrim_status launch_attn_paged(kvtrim_ctx* ctx, const CacheView& pool, const in
     {
         ProfScope prof(ctx, K_ATT_PARTIAL, st);
         ok = sh.head_dim == 128
-                 ? dispatch_partial<128>(sh.group, pool, q, sh, ws, chunk, scale_log2, nullptr, true, (unsigned)nb, ag.rpc, ag.extra_base, st)
-                 : dispatch_partial<64>(sh.group, pool, q, sh, ws, chunk, scale_log2, nullptr, true, (unsigned)nb, ag.rpc, ag.extra_base, st);
+                 ? dispatch_partial<128>(sh.group, pool, q, sh, ws, chunk, scale_log2, nullptr, true, (unsigned)nb, ag.round_rows, ag.extra_base, st)
+                 : dispatch_partial<64>(sh.group, pool, q, sh, ws, chunk, scale_log2, nullptr, true, (unsigned)nb, ag.round_rows, ag.extra_base, st);
     }
     if (!ok) return KVTRIM_EINVAL;
-    if (!tidy) return launch_combine(ctx, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, st, nb, ag.rpc, ag.extra_base);
+    if (!tidy) return launch_combine(ctx, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, st, nb, ag.round_rows, ag.chunk_rows, ag.extra_base);
     // the merge, and in the same launch one block per segment that tidies its block table
     CombineExtra ex{};
     ex.tidy = *tidy;
     const unsigned nblk = (unsigned)(sh.n_seq * (layer_end - layer_begin) * sh.n_kv_heads + sh.nseg);
     ProfScope prof(ctx, K_ATT_COMBINE, st);
     if (sh.head_dim == 128)
-        hipLaunchKernelGGL((k_att_combine<128, EXTRA_TIDY, true>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, ex, nb, ag.rpc, ag.extra_base);
+        hipLaunchKernelGGL((k_att_combine<128, EXTRA_TIDY, true>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, ex, nb, ag.round_rows, ag.chunk_rows, ag.extra_base);
     else
-        hipLaunchKernelGGL((k_att_combine<64, EXTRA_TIDY, true>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, ex, nb, ag.rpc, ag.extra_base);
+        hipLaunchKernelGGL((k_att_combine<64, EXTRA_TIDY, true>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, ws.att_chunk_prefix, layer_begin, layer_end, out, lse, ex, nb, ag.round_rows, ag.chunk_rows, ag.extra_base);
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;
 }
@@ -548,21 +573,21 @@ kvtrim_status launch_attn_paged(kvtrim_ctx* ctx, const CacheView& pool, const in
 // Merges the per-chunk partial results in ws.att_partial; chunk_prefix[g] .. chunk_prefix[g+1]
 // are the chunks of segment g.
 kvtrim_status launch_combine(kvtrim_ctx* ctx, const int32_t* chunk_prefix, int32_t layer_begin,
-                             int32_t layer_end, float* out, float* lse, hipStream_t st, int persist_nb, int rpc,
-                             int extra_base) {
+                             int32_t layer_end, float* out, float* lse, hipStream_t st, int persist_nb, int round_rows,
+                             int chunk_rows, int extra_base) {
     const Shape& sh = ctx->shape;
     const Workspace& ws = ctx->ws;
     const unsigned nblk = (unsigned)(sh.n_seq * (layer_end - layer_begin) * sh.n_kv_heads);
     ProfScope prof(ctx, K_ATT_COMBINE, st);
     if (persist_nb > 0) {
         if (sh.head_dim == 128)
-            hipLaunchKernelGGL((k_att_combine<128, EXTRA_NONE, true>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse, CombineExtra{}, persist_nb, rpc, extra_base);
+            hipLaunchKernelGGL((k_att_combine<128, EXTRA_NONE, true>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse, CombineExtra{}, persist_nb, round_rows, chunk_rows, extra_base);
         else
-            hipLaunchKernelGGL((k_att_combine<64, EXTRA_NONE, true>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse, CombineExtra{}, persist_nb, rpc, extra_base);
+            hipLaunchKernelGGL((k_att_combine<64, EXTRA_NONE, true>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse, CombineExtra{}, persist_nb, round_rows, chunk_rows, extra_base);
     } else if (sh.head_dim == 128)
-        hipLaunchKernelGGL((k_att_combine<128, EXTRA_NONE, false>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse, CombineExtra{}, 0, 1, 0);
+        hipLaunchKernelGGL((k_att_combine<128, EXTRA_NONE, false>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse, CombineExtra{}, 0, 1, 1, 0);
     else
-        hipLaunchKernelGGL((k_att_combine<64, EXTRA_NONE, false>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse, CombineExtra{}, 0, 1, 0);
+        hipLaunchKernelGGL((k_att_combine<64, EXTRA_NONE, false>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse, CombineExtra{}, 0, 1, 1, 0);
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;
 }
@@ -582,9 +607,9 @@ kvtrim_status launch_combine_unstage(kvtrim_ctx* ctx, const int32_t* chunk_prefi
     const unsigned nblk = (unsigned)(sh.n_seq * (layer_end - layer_begin) * sh.n_kv_heads + (max_chunks + per_block - 1) / per_block);
     ProfScope prof(ctx, K_ATT_COMBINE, st);
     if (sh.head_dim == 128)
-        hipLaunchKernelGGL((k_att_combine<128, EXTRA_UNSTAGE, false>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse, ex, 0, 1, 0);
+        hipLaunchKernelGGL((k_att_combine<128, EXTRA_UNSTAGE, false>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse, ex, 0, 1, 1, 0);
     else
-        hipLaunchKernelGGL((k_att_combine<64, EXTRA_UNSTAGE, false>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse, ex, 0, 1, 0);
+        hipLaunchKernelGGL((k_att_combine<64, EXTRA_UNSTAGE, false>), dim3(nblk), dim3(COMB_THREADS), 0, st, sh, ws, chunk_prefix, layer_begin, layer_end, out, lse, ex, 0, 1, 1, 0);
     KVTRIM_HIP(ctx, hipGetLastError());
     return KVTRIM_OK;
 }

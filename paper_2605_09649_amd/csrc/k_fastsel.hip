@@ -424,7 +424,8 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
             return layer >= lb && layer < le;
         };
         build_page_table<ATT_PAGE_GROUP>(pc, sh.nseg, in_range, ws.att_chunk_prefix, ws.att_desc, ws.max_att_chunks, nullptr,
-                                         ws.err, (int)blockIdx.x - sh.nseg * bps, (int)gridDim.x - sh.nseg * bps, ws.att_pages);
+                                         ws.err, (int)blockIdx.x - sh.nseg * bps, (int)gridDim.x - sh.nseg * bps, ws.att_pages,
+                                         ws.att_row_prefix);
         return;
     }
     // STEP: behind the scanning blocks the grid has one block per segment that only writes the segment's tables

@@ -391,7 +391,7 @@ __global__ __launch_bounds__(1024) void k_pg_att_plan(PagedView pc, Shape sh, Wo
     };
     static_assert(ATT_PAGE_GROUP == 4, "ws.att_pages holds four pages per chunk");
     build_page_table<ATT_PAGE_GROUP>(pc, sh.nseg, in_range, ws.att_chunk_prefix, ws.att_desc, ws.max_att_chunks, nullptr,
-                                     ws.err, blockIdx.x, gridDim.x, ws.att_pages);
+                                     ws.err, blockIdx.x, gridDim.x, ws.att_pages, ws.att_row_prefix);
 }
 
 // Mask of the paged selection: a block takes PG_PER_BLOCK pages, a thread four consecutive slots

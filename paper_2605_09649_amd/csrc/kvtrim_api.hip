@@ -106,6 +106,7 @@ static Layout layout_of(const kvtrim_config* c, bool select_only) {
     // a destination under a quarter of the source: at most max_entries / 4 rows in chunks of CMP_CHUNK, one ragged chunk per segment
     l.gat_slots = select_only ? 0 : c->max_entries / 4 + ((int64_t)nseg + 1) * CMP_CHUNK;
     l.off[38] = bump(cur, (size_t)l.gat_slots * sizeof(int32_t));              // gat_src
+    l.off[39] = bump(cur, seg_tables * (size_t)(nseg + 1) * sizeof(int64_t));  // att_row_prefix
     l.total = (cur + 255) & ~(size_t)255;
     return l;
 }
@@ -151,6 +152,7 @@ static void bind(const Layout& l, char* b, Workspace& w) {
     w.step_evl = (int32_t*)(b + l.off[36]);
     w.step_chunk_ev = (uint32_t*)(b + l.off[37]);
     w.gat_src = (int32_t*)(b + l.off[38]);
+    w.att_row_prefix = (int64_t*)(b + l.off[39]);
     w.gat_slots = l.gat_slots;
     w.fl_cap = l.fl_cap;
     w.max_sel_chunks = l.max_sel_chunks;

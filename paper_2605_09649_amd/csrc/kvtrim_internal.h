@@ -197,6 +197,7 @@ struct Workspace {
     // gathering fused kernel (sparse selections): the source row of every destination row, CMP_CHUNK slots per
     // destination chunk, written by the compaction scan
     int32_t* gat_src;            // [gat_slots]
+    int64_t* att_row_prefix;     // [nseg+1] attention: rows (paged: slots) of the layer range's segments before each segment
     int64_t gat_slots;
     int64_t max_sel_chunks, max_cmp_chunks, max_att_chunks;
 };
@@ -294,9 +295,10 @@ kvtrim_status launch_occupancy(kvtrim_ctx*, const CacheView&, const int32_t* now
 void launch_cmp_scan(kvtrim_ctx*, const CacheView& src, const uint8_t* keep, const int32_t* kept,
                      const CacheViewMut& dst, int32_t reserve, hipStream_t);
 // persist_nb > 0: the partial results are those of k_att_partial launched with that many blocks (one per block and
-// segment; rpc parts to a chunk, extra slots from extra_base on)
+// segment; shares start at multiples of round_rows, chunks have chunk_rows rows, extra slots from extra_base on)
 kvtrim_status launch_combine(kvtrim_ctx*, const int32_t* chunk_prefix, int32_t layer_begin, int32_t layer_end,
-                             float* out, float* lse, hipStream_t, int persist_nb = 0, int rpc = 1, int extra_base = 0);
+                             float* out, float* lse, hipStream_t, int persist_nb = 0, int round_rows = 1, int chunk_rows = 1,
+                             int extra_base = 0);
 // ... whose launch also finishes an in-place compaction: the rows parked in `stage` go to their places
 kvtrim_status launch_combine_unstage(kvtrim_ctx*, const int32_t* chunk_prefix, int32_t layer_begin, int32_t layer_end,
                                      float* out, float* lse, const CacheViewMut& c, const CacheViewMut& stage,

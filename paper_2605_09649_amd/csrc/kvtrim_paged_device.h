@@ -37,20 +37,22 @@ constexpr int ATT_PAGE_GROUP = 4;          // pages per attention chunk (512 row
 //               has them with the descriptor and not one dependent load later  (attention)
 // Built by `nparts` blocks: every block scans the per-segment counts (a few thousand integers),
 // block `part` fills the descriptors of the segments g = part (mod nparts), one wavefront per
-// segment, and block 0 writes the prefixes.  Returns the number of chunks.  Counts that do not
+// segment, and block 0 writes the prefixes (slot_prefix, optional: the slots - pages times the page size - of the
+// in-range segments before g).  Returns the number of chunks.  Counts that do not
 // fit raise ERR_LAYOUT and leave the table empty; a page id out of range raises it too and is
 // clamped, so that no reader leaves the pool.
 template <int GROUP, typename InRange>
 __device__ __forceinline__ int build_page_table(const PagedView& pc, int nseg, InRange in_range, int32_t* prefix,
                                                 ChunkDesc* desc, int64_t max_chunks, int64_t* entry_prefix,
-                                                int32_t* err, int part, int nparts, int32_t* pages_out = nullptr) {
+                                                int32_t* err, int part, int nparts, int32_t* pages_out = nullptr,
+                                                int64_t* slot_prefix = nullptr) {
     __shared__ uint64_t s_scan[17];
     __shared__ int s_bad;
     __shared__ int s_c0[1024], s_n[1024];
     const int tid = threadIdx.x;
     if (tid == 0) s_bad = 0;
     __syncthreads();
-    uint64_t carry = 0;
+    uint64_t carry = 0, slot_carry = 0;
     for (int base = 0; base < nseg; base += blockDim.x) {
         const int g = base + tid;
         uint64_t v = 0;
@@ -74,6 +76,12 @@ __device__ __forceinline__ int build_page_table(const PagedView& pc, int nseg, I
         if (g < nseg && part == 0) {
             prefix[g] = c0;
             if (entry_prefix) entry_prefix[g] = (int64_t)(ex >> 32);
+        }
+        if (slot_prefix) {                                           // slots of the in-range segments before g
+            uint64_t stot;
+            const uint64_t sex = slot_carry + block_excl_scan<uint64_t>((uint64_t)npg * P, s_scan, &stot);
+            slot_carry += stot;
+            if (g < nseg && part == 0) slot_prefix[g] = (int64_t)sex;
         }
         s_c0[tid] = c0;
         s_n[tid] = npg;
@@ -116,6 +124,7 @@ __device__ __forceinline__ int build_page_table(const PagedView& pc, int nseg, I
             for (int g = tid; g <= nseg; g += blockDim.x) {
                 prefix[g] = 0;
                 if (entry_prefix) entry_prefix[g] = 0;
+                if (slot_prefix) slot_prefix[g] = 0;
             }
         }
         __syncthreads();
@@ -124,6 +133,7 @@ __device__ __forceinline__ int build_page_table(const PagedView& pc, int nseg, I
     if (tid == 0 && part == 0) {
         prefix[nseg] = (int32_t)total;
         if (entry_prefix) entry_prefix[nseg] = (int64_t)(carry >> 32);
+        if (slot_prefix) slot_prefix[nseg] = (int64_t)slot_carry;
     }
     __syncthreads();
     return (int)total;

@@ -458,7 +458,9 @@ def test_attention_against_oracle_and_layer_ranges(D, G):
     kv.kvtrim_decode_attn(ctx, dc, q.to(DEV), 1, 2, scale, out2, None)
     o2 = out2.cpu().numpy()
     assert np.all(o2[:, 0] == 99.0) and np.all(o2[:, 2] == 99.0)
-    assert np.array_equal(o2[:, 1], o[:, 1])
+    # (the rows are shared out among the kernel's blocks per call, so the order of the fp32 sums - not their terms -
+    # depends on the layer range)
+    assert attn_error(o2[:, 1], o[:, 1]) <= 2e-6
 
 
 @pytest.mark.parametrize("blocks", [1, 2, 3, 7, 50, 100000])
