@@ -20,6 +20,7 @@
 namespace kvtrim {
 
 constexpr int ATT_THREADS = 256;
+constexpr int ATT_PLAN_BLOCKS = 16;         // blocks that share the filling of the chunk table
 
 typedef __attribute__((ext_vector_type(4))) float float4v;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -36,7 +37,7 @@ __global__ __launch_bounds__(1024) void k_att_plan(CacheView c, Shape sh, Worksp
         return layer >= layer_begin && layer < layer_end;
     };
     build_chunk_table(c.seg_len, c.seg_start, sh.nseg, in_range, chunk, c.cap, ws.att_chunk_prefix,
-                      ws.att_desc, max_chunks, ws.att_row_prefix, ws.err);
+                      ws.att_desc, max_chunks, ws.att_row_prefix, ws.err, (int)blockIdx.x, (int)gridDim.x);
 }
 
 template <int D>
@@ -523,7 +524,7 @@ kvtrim_status launch_attn(kvtrim_ctx* ctx, const CacheView& c, const uint16_t* q
     const int nb = ag.nb;
     const float scale_log2 = scale * 1.4426950408889634f;
     { ProfScope prof(ctx, K_ATT_PLAN, st);
-      hipLaunchKernelGGL(k_att_plan, dim3(1), dim3(1024), 0, st, c, sh, ws, chunk, layer_begin, layer_end, max_chunks); }
+      hipLaunchKernelGGL(k_att_plan, dim3(ATT_PLAN_BLOCKS), dim3(1024), 0, st, c, sh, ws, chunk, layer_begin, layer_end, max_chunks); }
     bool ok;
     {
         ProfScope prof(ctx, K_ATT_PARTIAL, st);

@@ -96,13 +96,15 @@ __device__ __forceinline__ void for_each_ranked_seq(const SelState* __restrict__
 // empty).  Optionally writes entry_prefix[g] = entries of the in-range segments before g
 // (entry_prefix[nseg] = all of them).
 // Segments with few chunks are filled by the thread that scanned them; long ones are queued
-// in LDS and filled by whole wavefronts.
+// in LDS and filled by whole wavefronts.  The table may be built by `nparts` blocks: every block
+// scans all segments, block `part` fills the descriptors of the segments g = part (mod nparts),
+// and block 0 writes the prefixes.
 template <typename InRange>
 __device__ __forceinline__ int build_chunk_table(const int32_t* __restrict__ seg_len,
                                                  const int64_t* __restrict__ seg_start, int nseg,
                                                  InRange in_range, int chunk, int64_t cap,
                                                  int32_t* prefix, ChunkDesc* desc, int64_t max_chunks,
-                                                 int64_t* entry_prefix, int32_t* err) {
+                                                 int64_t* entry_prefix, int32_t* err, int part = 0, int nparts = 1) {
     constexpr int SMALL = 16;
     __shared__ uint64_t s_scan[17];
     __shared__ int s_bad, s_nbig;
@@ -129,9 +131,11 @@ __device__ __forceinline__ int build_chunk_table(const int32_t* __restrict__ seg
     const int64_t total = (int64_t)(carry & 0xffffffffu);
     if (s_bad || total > max_chunks || (carry >> 32) > (uint64_t)cap) {
         if (threadIdx.x == 0) atomicOr(err, ERR_LAYOUT);
-        for (int g = threadIdx.x; g <= nseg; g += blockDim.x) {
-            prefix[g] = 0;
-            if (entry_prefix) entry_prefix[g] = 0;
+        if (part == 0) {
+            for (int g = threadIdx.x; g <= nseg; g += blockDim.x) {
+                prefix[g] = 0;
+                if (entry_prefix) entry_prefix[g] = 0;
+            }
         }
         __syncthreads();
         return 0;
@@ -154,9 +158,11 @@ __device__ __forceinline__ int build_chunk_table(const int32_t* __restrict__ seg
         carry += tot;
         const int c0 = (int)(ex & 0xffffffffu);
         const int n = (int)(v & 0xffffffffu);
-        if (g < nseg) {
+        if (g < nseg && part == 0) {
             prefix[g] = c0;
             if (entry_prefix) entry_prefix[g] = (int64_t)(ex >> 32);
+        }
+        if (g < nseg && g % nparts == part) {
             if (n > SMALL) {
                 const int slot = atomicAdd(&s_nbig, 1);
                 s_big_g[slot] = g;
@@ -188,7 +194,7 @@ __device__ __forceinline__ int build_chunk_table(const int32_t* __restrict__ seg
         }
         __syncthreads();
     }
-    if (threadIdx.x == 0) {
+    if (threadIdx.x == 0 && part == 0) {
         prefix[nseg] = (int32_t)(carry & 0xffffffffu);
         if (entry_prefix) entry_prefix[nseg] = (int64_t)(carry >> 32);
     }
