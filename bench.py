@@ -489,11 +489,17 @@ def moved_bytes(w, a, n_cand, n_ret, rows_written_in_place=None):
         # (in the one call the eviction rides in the mask kernel, which reads the positions anyway)
         m["attend"] = (4 * D + 4) * n_ret + 6 * D * nq             # K, V and position of every live slot; q in, out out
     elif a.inplace:
-        per_ip = n_cand + R * n_ret + R * (rows_written_in_place or 0) + 6 * D * nq
-        per_oop = n_cand + 2 * R * n_ret + 6 * D * nq
-        m["compact_attn (in place; one step in %d out of place)" % a.inplace] = ((a.inplace - 1) * per_ip + per_oop) // a.inplace
+        moved = rows_written_in_place or 0
         if a.unfused:
+            # stage 3 alone in place touches only the rows that move (read and written once); the attention reads all
+            per_ip = n_cand + 2 * R * moved
+            per_oop = n_cand + 2 * R * n_ret
+            m["compact (in place; one step in %d out of place)" % a.inplace] = ((a.inplace - 1) * per_ip + per_oop) // a.inplace
             m["decode_attn"] = 4 * D * n_ret + 6 * D * nq
+        else:
+            per_ip = n_cand + R * n_ret + R * moved + 6 * D * nq
+            per_oop = n_cand + 2 * R * n_ret + 6 * D * nq
+            m["compact_attn (in place; one step in %d out of place)" % a.inplace] = ((a.inplace - 1) * per_ip + per_oop) // a.inplace
     elif a.unfused:
         m["compact"] = n_cand + 2 * R * n_ret
         m["decode_attn"] = 4 * D * n_ret + 6 * D * nq
