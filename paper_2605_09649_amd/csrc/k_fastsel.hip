@@ -807,12 +807,23 @@ __global__ __launch_bounds__(FAST_THREADS) void k_fast_scan(CacheView c, const i
                         }
                     }
                     __syncthreads();
-                    if (tid < bcnt) {
-                        const uint32_t mk = sm.g_key[tid];
-                        const int ms = sm.g_seg[tid], mp = sm.g_pos[tid];
+                    {
+                        // four threads to an entry (bcnt <= 256 = a quarter of the block), each against every fourth
+                        // of the others; the triples are compared without branches, so the loop's LDS reads do not
+                        // wait for one another (with the short-circuit form an iteration took three dependent reads)
+                        static_assert(4 * FAST_BIN_DIRECT <= FAST_THREADS, "four threads rank one entry");
+                        const int me = min(tid >> 2, bcnt - 1);
+                        const uint32_t mk = sm.g_key[me];
+                        const int ms = sm.g_seg[me], mp = sm.g_pos[me];
                         int rank = 0;
-                        for (int j = 0; j < bcnt; ++j) rank += evicted_before(sm.g_key[j], sm.g_seg[j], sm.g_pos[j], mk, ms, mp);
-                        if (rank == (int)(r - before)) {
+                        for (int j = tid & 3; j < bcnt; j += 4) {
+                            const uint32_t kj = sm.g_key[j];
+                            const int sj = sm.g_seg[j], pj = sm.g_pos[j];
+                            rank += (int)((kj < mk) | ((kj == mk) & ((sj > ms) | ((sj == ms) & (pj > mp)))));
+                        }
+                        rank += __shfl_xor(rank, 1, 64);
+                        rank += __shfl_xor(rank, 2, 64);
+                        if ((tid >> 2) < bcnt && (tid & 3) == 0 && rank == (int)(r - before)) {
                             sm.found_key = mk;
                             sm.found_seg = ms;
                             sm.found_pos = mp;
