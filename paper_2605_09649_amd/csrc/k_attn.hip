@@ -316,6 +316,7 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
 // the tile with loads that do not depend on each other, so all of them are in flight at once.
 constexpr int COMB_TILE = 128;
 constexpr int COMB_THREADS = 512;
+static_assert(COMB_THREADS / 64 >= 8, "one wavefront of the merge kernel per query head of a group");
 // Housekeeping that nothing in this launch reads rides behind the merging blocks of the grid, so that it needs no
 // launch of its own:
 //   EXTRA_TIDY (the paged decode step in one call): one block per segment takes the pages emptied by the step's
@@ -411,12 +412,19 @@ __global__ __launch_bounds__(COMB_THREADS) void k_att_combine(Shape sh, Workspac
             s_l[i / G][i % G] = slot < 0 ? 0.f : p[1];
         }
         __syncthreads();
-        if (tid < G) {                                            // running maximum and rescale factor per query head
-            float tm = s_M[tid];
-            for (int i = 0; i < nt; ++i) tm = fmaxf(tm, s_m[i][tid]);
-            const float ms = tm == -INFINITY ? 0.f : tm;
-            s_a[tid] = __builtin_amdgcn_exp2f(s_M[tid] - ms);
-            s_M[tid] = tm;
+        const int wv = tid >> 6, ln = tid & 63;                    // wavefront g of the block serves query head g (G <= 8 wavefronts)
+        if (wv < G) {                                             // running maximum and rescale factor per query head
+            float tm = -INFINITY;
+            for (int i = ln; i < nt; i += 64) tm = fmaxf(tm, s_m[i][wv]);
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) tm = fmaxf(tm, __shfl_xor(tm, d, 64));
+            if (ln == 0) {
+                const float old = s_M[wv];
+                tm = fmaxf(tm, old);
+                const float ms = tm == -INFINITY ? 0.f : tm;
+                s_a[wv] = __builtin_amdgcn_exp2f(old - ms);
+                s_M[wv] = tm;
+            }
         }
         __syncthreads();
         for (int i = tid; i < nt * G; i += COMB_THREADS) {
@@ -424,10 +432,12 @@ __global__ __launch_bounds__(COMB_THREADS) void k_att_combine(Shape sh, Workspac
             s_w[i / G][i % G] = __builtin_amdgcn_exp2f(s_m[i / G][i % G] - (M == -INFINITY ? 0.f : M));
         }
         __syncthreads();
-        if (tid < G) {
-            float lv = s_L[tid] * s_a[tid];
-            for (int i = 0; i < nt; ++i) lv += s_l[i][tid] * s_w[i][tid];
-            s_L[tid] = lv;
+        if (wv < G) {
+            float lv = 0.f;
+            for (int i = ln; i < nt; i += 64) lv += s_l[i][wv] * s_w[i][wv];
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) lv += __shfl_xor(lv, d, 64);
+            if (ln == 0) s_L[wv] = s_L[wv] * s_a[wv] + lv;
         }
 #pragma unroll
         for (int p = 0; p < PAIRS; ++p) {

@@ -159,9 +159,11 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
         static_assert(sizeof(StepSegRec) == 64 && STEP_REC_IDX == 12, "one word per lane: dst_start, cnt, off, twelve indices");
         const int32_t* rw = reinterpret_cast<const int32_t*>(ws.step_rec + cd.seg);
         step_recw = lane < 16 ? rw[lane] : 0;
-        step_idx0 = (int)(sbase - src.seg_start[cd.seg]);
     };
     auto step_resolve = [&]() {
+        // (the segment's start is read here and not with the record: it is a scalar load that depends on the descriptor,
+        // and the wait for it would stand between the descriptor and the requests for the rows)
+        step_idx0 = (int)(sbase - src.seg_start[cd.seg]);
         step_cnt = __builtin_amdgcn_readlane(step_recw, 2);
         const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane(step_recw, 0), hi = (uint32_t)__builtin_amdgcn_readlane(step_recw, 1);
         step_more = ws.step_evl + (size_t)(cd.seg / sh.segs_per_seq) * STEP_MAX_EVICT + __builtin_amdgcn_readlane(step_recw, 3);
@@ -238,7 +240,6 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
     const int seq = seg / sh.segs_per_seq, lh = seg % sh.segs_per_seq;
     const int layer = lh / sh.n_kv_heads, head = lh % sh.n_kv_heads;
     const bool attend = layer >= layer_begin && layer < layer_end;   // uniform over the block
-    if (STEP && tid == 0 && sbase == src.seg_start[seg]) step_seg_len[seg] = ws.step_len[seg];   // the segment's first chunk
     const int sub = lane >> 4, col = lane & 15;
     const int r0 = wave * CMP_WAVE_ROWS;                          // this wavefront's rows of the survivor list
     const bool has_rows = r0 < cnt;                               // uniform over the wavefront
@@ -394,6 +395,9 @@ __global__ __launch_bounds__(FUS_THREADS) void k_cmp_attn(CacheView src, const u
             if (attend) attend_rows(kk, vv, qp);
         }
     }
+    // the segment's first chunk commits the source segment's new length (after the rows have been asked for: the look
+    // at the segment's start is a load that depends on the descriptor)
+    if (STEP && tid == 0 && sbase == src.seg_start[seg]) step_seg_len[seg] = ws.step_len[seg];
     if (!attend) return;
 
     // the partials of the wavefronts that had rows are merged by all threads
