@@ -105,25 +105,28 @@ __global__ __launch_bounds__(ATT_THREADS) void k_att_partial(CacheView c, const 
     if ((int)blockIdx.x >= nb) return;
     const int64_t* rp = ws.att_row_prefix;
     const int64_t N = rp[sh.nseg];
-    // where row e of the concatenation lies: the segment s with rp[s] <= e < rp[s + 1], and the round of 64 rows inside it
-    auto locate = [&](int64_t e, int& seg_at, int& row_at) {
-        if (e >= N) {
-            seg_at = sh.nseg;
-            row_at = 0;
-            return;
-        }
-        int lo = 0, hi = sh.nseg;                                 // invariant: rp[lo] <= e < rp[hi]
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (rp[mid] <= e) lo = mid;
-            else hi = mid;
-        }
-        seg_at = lo;
-        row_at = (int)(e - rp[lo]) / round_rows * round_rows;
-    };
+    // where the rows e0 <= e1 of the concatenation lie: the segment s with rp[s] <= e < rp[s + 1] (nseg behind the last row)
+    // and the round of rows inside it.  A 64-way search, both rows at once: every lane looks at one point of each
+    // remaining range, so 4096 segments take two rounds of one load instead of twelve loads one after the other.
     int seg_b, row_b, seg_e, row_e;
-    locate((int64_t)blockIdx.x * N / nb, seg_b, row_b);
-    locate((int64_t)(blockIdx.x + 1) * N / nb, seg_e, row_e);
+    {
+        const int64_t e0 = (int64_t)blockIdx.x * N / nb, e1 = (int64_t)(blockIdx.x + 1) * N / nb;
+        int lo0 = 0, hi0 = sh.nseg, lo1 = 0, hi1 = sh.nseg;        // invariant: rp[lo] <= e < rp[hi]   (rp[0] = 0, rp[nseg] = N)
+        while (hi0 - lo0 > 1 || hi1 - lo1 > 1) {
+            const int st0 = (hi0 - lo0 + 63) / 64, st1 = (hi1 - lo1 + 63) / 64;   // lane l probes lo + (l + 1) stride
+            const int i0 = lo0 + (lane + 1) * st0, i1 = lo1 + (lane + 1) * st1;
+            const bool in0 = i0 < hi0 && rp[min(i0, sh.nseg)] <= e0, in1 = i1 < hi1 && rp[min(i1, sh.nseg)] <= e1;
+            const int n0 = __popcll(__ballot(in0)), n1 = __popcll(__ballot(in1));   // (monotone: the first n lanes)
+            hi0 = min(hi0, lo0 + (n0 + 1) * st0);
+            lo0 += n0 * st0;
+            hi1 = min(hi1, lo1 + (n1 + 1) * st1);
+            lo1 += n1 * st1;
+        }
+        seg_b = e0 >= N ? sh.nseg : lo0;
+        row_b = e0 >= N ? 0 : (int)(e0 - rp[lo0]) / round_rows * round_rows;
+        seg_e = e1 >= N ? sh.nseg : lo1;
+        row_e = e1 >= N ? 0 : (int)(e1 - rp[lo1]) / round_rows * round_rows;
+    }
     if (seg_b == seg_e && row_b == row_e) return;                 // (shares of less than a round: a later block has the rows)
     const int c16 = lane & 15, b4 = lane >> 4;
     const vec* kp = reinterpret_cast<const vec*>(c.k);
