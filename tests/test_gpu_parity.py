@@ -491,6 +491,44 @@ def test_attention_for_any_size_of_the_fixed_grid(blocks, monkeypatch):
         assert np.array_equal(np.isneginf(l), ~fin)
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_attention_on_random_shapes_ranges_and_grids(seed, monkeypatch):
+    # random segment lengths (many empty or tiny ones beside long ones), a random layer range and a random number of
+    # blocks for the attention kernel's fixed grid: the shares of the blocks start and end anywhere
+    rng = np.random.default_rng(1000 + seed)
+    S, L, H = int(rng.integers(1, 4)), int(rng.integers(1, 4)), int(rng.integers(1, 4))
+    G, D = int(rng.choice([1, 2, 4, 7])), int(rng.choice([64, 128]))
+    monkeypatch.setenv("KVTRIM_ATT_BLOCKS", str(int(rng.choice([1, 2, 3, 5, 9, 17, 40, 768]))))
+    w = wl(S, L, H, G, D)
+    kinds = rng.integers(0, 5, w.nseg)
+    seg_len = np.where(kinds == 0, 0, np.where(kinds == 1, rng.integers(1, 70, w.nseg),
+                       np.where(kinds == 2, rng.integers(400, 700, w.nseg), rng.integers(1000, 6000, w.nseg))))
+    c, _ = ki.ragged_cache(w, seg_len, salt=30 + seed)
+    hc = host_cache(w, c)
+    dc = kv.Cache.from_dict(c, DEV)
+    ctx = kv.Context(S, L, H, H * G, D, hc.cap)
+    q = ki.decode_inputs(w, seed)["q"]
+    scale = 1.0 / math.sqrt(D)
+    ref, ref_lse = oracle.attend(hc, bf16_bits(q), scale)
+    lb = int(rng.integers(0, L))
+    le = int(rng.integers(lb + 1, L + 1))
+    out = torch.full(ref.shape, 99.0, dtype=torch.float32, device=DEV)
+    lse = torch.full(ref_lse.shape, 99.0, dtype=torch.float32, device=DEV)
+    kv.kvtrim_decode_attn(ctx, dc, q.to(DEV), lb, le, scale, out, lse)
+    assert kv.kvtrim_poll_error(ctx) == 0
+    o, l = out.cpu().numpy(), lse.cpu().numpy()
+    outside = [x for x in range(L) if not lb <= x < le]
+    assert np.all(o[:, outside] == 99.0) and np.all(l[:, outside] == 99.0)
+    if np.abs(ref[:, lb:le]).max() > 0:
+        assert attn_error(o[:, lb:le], ref[:, lb:le]) <= ATTN_TOL, (seed, seg_len.tolist(), lb, le)
+    else:
+        assert np.all(o[:, lb:le] == 0.0)
+    fin = np.isfinite(ref_lse[:, lb:le])
+    assert np.array_equal(np.isneginf(l[:, lb:le]), ~fin)
+    if fin.any():
+        assert np.abs(l[:, lb:le][fin] - ref_lse[:, lb:le][fin]).max() <= 2e-3
+
+
 def test_attention_with_large_logits_stays_finite():
     w = wl(1, 1, 1, 4, 128)
     c, _ = ki.ragged_cache(w, [900], salt=10)
