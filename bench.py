@@ -521,7 +521,7 @@ def run_decode(args, brief=False):
 
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    w = ki.workload(args.workload, prefill=args.prefill)
+    w = ki.workload(args.workload, prefill=args.prefill, seed_index=args.seed)
     reserve = args.inplace if args.inplace else 1                 # free slots behind every segment after an out-of-place step
     K, W = args.steps, max(args.warmup, 1)
     cpu_steps = 0 if args.no_cpu_baseline else args.cpu_steps
@@ -717,6 +717,7 @@ def run_decode(args, brief=False):
                         f"{w.prefill[0] if w.n_seq == 1 else 'lengths ' + str(min(w.prefill)) + '..' + str(max(w.prefill))} prefilled, "
                         f"B={B} ({n_cand} candidates/step, {n_ret} retained), "
                         f"score lookahead horizon {args.horizon if args.horizon > 0 else 'infinite'}",
+            "seed_index": args.seed,
             "stages": calls,
             "first_step_ms": first_ms,
             "first_step_kernels_ms": first_kernels_ms,
@@ -931,6 +932,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="long", choices=["long", "llama", "vlm", "tiny", "multiturn"])
     ap.add_argument("--prefill", type=int, default=None, help="override the prefilled length (scaled-down run)")
+    ap.add_argument("--seed", type=int, default=0, metavar="I",
+                    help="another seeded draw of every random input of the workload's recipe (0: the default inputs)")
     ap.add_argument("--horizon", type=int, default=1,
                     help="lookahead horizon of the score: 1 = the metric's form, 2 = the paper's inference default, 0 = infinite")
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -41,6 +41,7 @@ class Workload:
     evidence_z: Tuple[float, float] = (8.0, 1.0)
     visual_block: Tuple[int, int] = (0, 0)            # [begin, end) positions of the visual tokens
     visual_z: Tuple[float, float] = (1.5, 2.0)
+    seed_index: int = 0                               # which of several seeded repetitions of the workload this is
 
     @property
     def nseg(self):
@@ -52,15 +53,16 @@ class Workload:
 
     @property
     def seed(self):
-        return BASE_SEED + self.index
+        return BASE_SEED + self.index + 1000 * self.seed_index
 
     def seg_id(self, seq, layer, head):
         return (seq * self.n_layers + layer) * self.n_kv_heads + head
 
 
-def workload(name: str, prefill: int = None) -> Workload:
+def workload(name: str, prefill: int = None, seed_index: int = 0) -> Workload:
     """One of 'tiny', 'llama', 'long', 'vlm', 'multiturn'.  `prefill` overrides the
-    prefilled length (budget fractions are kept) to scale a workload down."""
+    prefilled length (budget fractions are kept) to scale a workload down; `seed_index` > 0 gives
+    another draw of every random input of the same recipe."""
     if name == "tiny":
         T = prefill or 2048
         w = Workload("tiny", 0, 1, 4, 4, 8, 64, (T,), (max(1, T // 2),), 16, 3.0, 1.5)
@@ -85,7 +87,7 @@ def workload(name: str, prefill: int = None) -> Workload:
         w = Workload("multiturn", 4, 16, 32, 8, 32, 128, lens, (per_head * 32 * 8,) * 16, 64, 3.0, 1.5)
     else:
         raise ValueError(name)
-    return w
+    return replace(w, seed_index=seed_index) if seed_index else w
 
 
 def _gen(w: Workload, device, *salt):
