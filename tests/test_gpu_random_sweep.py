@@ -1,6 +1,7 @@
-"""Seeded sweep over small random configurations: shapes, ragged and empty segments, budgets from 0 to above
-the entry count, quantised log beta (exact score ties everywhere) - the ragged loop (two-call and fused) and the
-paged loop against the oracle, every stage compared as in the other parity tests."""
+"""Seeded sweep over random configurations: shapes, ragged and empty segments (small ones, and segments of up to
+40,000 entries beside tiny ones), budgets from 0 to above the entry count, quantised log beta (exact score ties
+everywhere) - the ragged loop (two-call and fused) and the paged loop against the oracle, every stage compared as
+in the other parity tests."""
 import numpy as np
 import pytest
 import torch
@@ -14,17 +15,21 @@ DEV = "cuda:0"
 ATTN_TOL = 5e-3
 
 
-def random_case(seed, reserve=1):
-    rng = np.random.default_rng(1000 + seed)
+def random_case(seed, reserve=1, long_segments=False):
+    """long_segments: segments of up to 40,000 entries (several blocks of the scoring kernel and many chunks of the
+    row mover and the attention per segment) beside empty and tiny ones; budgets mostly a few hundred under the count."""
+    rng = np.random.default_rng((5000 if long_segments else 1000) + seed)
     S = int(rng.integers(1, 4))
     L = int(rng.integers(1, 4))
     H = int(rng.integers(1, 4))
     G = int(rng.integers(1, 9))
     D = int(rng.choice([64, 128]))
     w = ki.Workload("r", 0, S, L, H, G * H, D, (0,) * S, (0,) * S, 1, 3.0, 1.5)
-    hi = int(rng.choice([5, 150, 700, 2600]))
+    hi = int(rng.choice([4000, 9000, 20000, 40000] if long_segments else [5, 150, 700, 2600]))
     seg_len = rng.integers(0, hi + 1, w.nseg)
     seg_len[rng.random(w.nseg) < 0.2] = 0
+    if long_segments:
+        seg_len[rng.random(w.nseg) < 0.2] = rng.integers(1, 130)
     c, now = ki.ragged_cache(w, seg_len, reserve=reserve, salt=seed, pos_stride_max=int(rng.integers(1, 5)))
     if rng.random() < 0.5:                                         # few distinct retention values: ties at the threshold
         g = torch.Generator().manual_seed(seed)
@@ -38,14 +43,26 @@ def random_case(seed, reserve=1):
         b = []
         for n in per_seq:
             kind = rng.random()
-            b.append(0 if kind < 0.1 else (10 ** 6 if kind < 0.2 else int(rng.integers(1, max(2, n + 10)))))
+            if long_segments and 0.2 <= kind < 0.6:
+                b.append(max(1, n - int(rng.integers(0, 400))))
+            else:
+                b.append(0 if kind < 0.1 else (10 ** 7 if kind < 0.2 else int(rng.integers(1, max(2, n + 10)))))
         budgets.append(b)
     return w, c, now, budgets
 
 
 @pytest.mark.parametrize("seed", range(48))
 def test_random_configuration(seed):
-    w, c, now, budgets = random_case(seed)
+    check_case(seed, False)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_configuration_with_long_segments(seed):
+    check_case(seed, True)
+
+
+def check_case(seed, long_segments):
+    w, c, now, budgets = random_case(seed, long_segments=long_segments)
     clone = lambda: {k: (v.clone() if torch.is_tensor(v) else v) for k, v in c.items()}
     for fused in (False, True):
         # the ragged harness takes one budget for all steps: the first of the list
@@ -56,7 +73,7 @@ def test_random_configuration(seed):
             assert r["attn_err"] <= ATTN_TOL and r["lse_err"] <= 2e-3 and r["lse_inf_equal"], (seed, fused, i, r)
     # the same configuration compacted inside the cache (fused for even seeds, stage 3 alone + attention for odd ones),
     # with an out-of-place step in between where there are at least three steps
-    w2, c2, now2, budgets2 = random_case(seed, reserve=len(budgets) + 1)
+    w2, c2, now2, budgets2 = random_case(seed, reserve=len(budgets) + 1, long_segments=long_segments)
     res = run_steps_inplace_both(w2, len(budgets2), budgets2[0], len(budgets2) + 1, c2, now2.numpy(), device=DEV,
                                  two_call=bool(seed % 2), rebalance_at=(1,) if len(budgets2) > 2 else (),
                                  rebalance_room=lambda step: len(budgets2) - step - 1)   # budgets above the count evict nothing

@@ -119,10 +119,10 @@ def test_quantised_retention_gives_ties_at_the_threshold_every_step(levels):
               (levels, hint))
 
 
-@pytest.mark.parametrize("seed", range(24))
-def test_random_configuration(seed):
+@pytest.mark.parametrize("seed,long_segments", [(s, False) for s in range(24)] + [(s, True) for s in range(12)])
+def test_random_configuration(seed, long_segments):
     from test_gpu_random_sweep import random_case
-    w, c, now, budgets = random_case(seed)
+    w, c, now, budgets = random_case(seed, long_segments=long_segments)
     for hint in (0, 1 + seed % 7, 900):
         clone = {k: (v.clone() if torch.is_tensor(v) else v) for k, v in c.items()}
         res = run_steps_both(w, steps=len(budgets), budget=[max(b[s] for b in budgets) for s in range(w.n_seq)], device=DEV,
