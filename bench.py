@@ -150,9 +150,11 @@ def bench_gate(args):
     else:
         first, second = "k_gate_hidden", "k_gate_dot" if "k_gate_dot" in prof else "k_gate_readout"
         h_ms = prof[first][0] / prof[first][1]
-        r_ms = prof[second][0] / prof[second][1]
-        # first layer: W1 once per 64 tokens of a call, x once per 16-row tile group (cached), u written once
-        alg_hidden = w1_bytes + L * n_tok * dm * 2 + L * n_tok * dg * 4
+        # (prepared weights, up to 16 tokens: the readout rides in the first-layer kernel and there is no second one)
+        r_ms = prof[second][0] / prof[second][1] if second in prof else None
+        # first layer: W1 once per 64 tokens of a call, x once per 16-row tile group (cached), u written once (one
+        # kernel: the folded vectors read, per block its parts of the readout sums written and read once instead)
+        alg_hidden = w1_bytes + L * n_tok * dm * 2 + (L * n_tok * dg * 4 if r_ms is not None else L * H * (dg + 1) * 4 + 2 * L * (dg // 16) * H * n_tok * 4)
         if n_tok <= 64:
             roof = {"bound": "hbm", "kernel": first, "achieved": alg_hidden / (h_ms * 1e-3) / 1e9,
                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": measured_traffic(f"gate_decode_{n_tok}tok", first),

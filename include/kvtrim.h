@@ -504,7 +504,9 @@ kvtrim_status kvtrim_gate_forward(kvtrim_ctx *ctx, const kvtrim_gate *g, const v
  * kvtrim_gate_forward_prepared: same arguments, outputs and arithmetic contract as kvtrim_gate_forward (g must
  * be the gate the buffer was prepared from; scratch as for kvtrim_gate_forward); calls of every length then read
  * the readout as one dot product per (token, layer, head), and the one-kernel path that kvtrim_gate_forward
- * takes from 128 tokens on is taken from 24 tokens on, reading W1 from the operand-order copy. */
+ * takes from 128 tokens on is taken from 24 tokens on, reading W1 from the operand-order copy.  Calls of up to 16
+ * tokens (with at most 16 KV heads) are one kernel as well; it keeps one arrival counter per layer in the context's
+ * workspace, so - as for every call on a context - two gate calls on one context must not run at the same time. */
 size_t kvtrim_gate_prepared_bytes(const kvtrim_gate *g, int32_t n_layers, int32_t n_kv_heads);
 kvtrim_status kvtrim_gate_prepare(kvtrim_ctx *ctx, const kvtrim_gate *g, void *prepared, void *hip_stream);
 kvtrim_status kvtrim_gate_forward_prepared(kvtrim_ctx *ctx, const kvtrim_gate *g, const void *prepared, const void *x,

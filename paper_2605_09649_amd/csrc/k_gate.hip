@@ -41,6 +41,22 @@ struct GateView {
     int d_model, d_g, d_p;
 };
 
+__device__ __forceinline__ float log_sigmoid(float z) {
+    return z >= 0.f ? -log1pf(expf(-z)) : z - log1pf(expf(z));
+}
+
+// log sum_{k<H} beta^k from log(beta); H <= 0: the limit -log(1 - beta)
+__device__ __forceinline__ float log_tail_of(float lb, int horizon) {
+    if (horizon <= 0) return -logf(-expm1f(lb));
+    const float beta = expf(lb);
+    float sum = 0.f, term = 1.f;
+    for (int k = 0; k < horizon; ++k) {
+        sum += term;
+        term *= beta;
+    }
+    return logf(sum);
+}
+
 constexpr int GH_THREADS = 256;          // four wavefronts split d_model
 constexpr int GH_ROWS = 16;
 
@@ -50,10 +66,26 @@ constexpr int GH_ROWS = 16;
 // rows: with more than 16 tokens a block takes MT = 4 tiles of W1 so that x is read by a quarter of the blocks.
 // TILED: W1 comes from the operand-order copy of a prepared buffer (`tiled` points at the first layer of the
 // range: [layer][16-row tile][64-wide step][half][lane] 16-byte pieces), so a wavefront load reads 1 KB in one piece.
-template <int NT, int MT, bool TILED>
+// DOT (one tile of tokens, one tile of rows, prepared weights): the readout from the folded vectors happens here as
+// well, so u never goes to memory and the call is one kernel.  z = v . u + s is a sum over the hidden units, of which
+// a block holds 16: it leaves its part of every (token, head) sum in `part` ([layer][block][head][token], the
+// caller's scratch buffer), and the block of a layer that arrives last (one counter per layer, left at zero) adds
+// the parts in block order - the same order whichever block that is.
+struct GateDot {
+    const float* v;          // [layers of the range][heads][d_g]
+    const float* s;          // [layers of the range][heads]
+    float* part;
+    uint32_t* done;          // [layers of the range]
+    float* log_beta_out;
+    float* log_tail_out;
+    int n_heads, n_layers, horizon;
+};
+
+template <int NT, int MT, bool TILED, bool DOT>
 __global__ __launch_bounds__(GH_THREADS) void k_gate_hidden(GateView g, const uint16_t* __restrict__ x, int n_tok,
                                                             int layer_begin, const uint4* __restrict__ tiled,
-                                                            float* __restrict__ u) {
+                                                            float* __restrict__ u, GateDot dot) {
+    static_assert(!DOT || (NT == 1 && MT == 1 && TILED), "the readout rides in the 16 x 16 instance only");
     __shared__ float s_part[4][NT][16 * MT][17];
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int r16 = lane & 15, g4 = lane >> 4;
@@ -82,6 +114,14 @@ __global__ __launch_bounds__(GH_THREADS) void k_gate_hidden(GateView g, const ui
     for (int m = 0; m < MT; ++m)
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[m][t] = gate_f4{0.f, 0.f, 0.f, 0.f};
+    // DOT: the folded vectors' entries for this thread's hidden unit, asked for before the stream of W1 starts
+    constexpr int DOT_HEADS = DOT ? 16 : 1;
+    float vh[DOT_HEADS];
+    if (DOT) {
+#pragma unroll
+        for (int h = 0; h < DOT_HEADS; ++h)
+            vh[h] = h < dot.n_heads ? dot.v[((size_t)lr * dot.n_heads + h) * g.d_g + row0 + (tid & 15)] : 0.f;
+    }
 
     // 64 contraction indices per step (8 uint4 of a row); AHEAD steps of weights are loaded ahead
     constexpr int AHEAD = MT == 1 ? 4 : 2;
@@ -128,6 +168,55 @@ __global__ __launch_bounds__(GH_THREADS) void k_gate_hidden(GateView g, const ui
             for (int r = 0; r < 4; ++r) s_part[wave][t][16 * m + 4 * g4 + r][r16] = acc[m][t][r];
     __syncthreads();
     constexpr int ROWS = 16 * MT;
+    if (DOT) {
+        static_assert(GH_THREADS == 256, "one (hidden unit, token) pair per thread");
+        __shared__ int s_last;
+        const int row = tid & 15, tok = tid >> 4;                   // (a token's 16 hidden units sit in 16 neighbouring lanes)
+        const int nblk = gridDim.x;
+        float su = 0.f;
+        if (tok < n_tok) {
+            const float a = s_part[0][0][row][tok] + s_part[1][0][row][tok] + s_part[2][0][row][tok] + s_part[3][0][row][tok] +
+                            g.c1[(size_t)layer * g.d_g + row0 + row];
+            su = a / (1.0f + __expf(-a));
+        }
+#pragma unroll
+        for (int h = 0; h < DOT_HEADS; ++h) {
+            if (h >= dot.n_heads) break;                          // (uniform)
+            float p = su * vh[h];
+            p += __shfl_xor(p, 1, 64);
+            p += __shfl_xor(p, 2, 64);
+            p += __shfl_xor(p, 4, 64);
+            p += __shfl_xor(p, 8, 64);
+            if (row == 0 && tok < n_tok)
+                __hip_atomic_store(&dot.part[(((size_t)lr * nblk + blockIdx.x) * dot.n_heads + h) * n_tok + tok], p, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // this thread's parts are acknowledged ...
+        __syncthreads();                                          // ... and so are the whole block's, before it arrives
+        if (tid == 0) s_last = atomicAdd(&dot.done[lr], 1u) == (unsigned)nblk - 1u;
+        __syncthreads();
+        if (!s_last) return;
+        if (tid == 0) __hip_atomic_store(&dot.done[lr], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // (for the next call)
+        for (int item = tid; item < n_tok * dot.n_heads; item += GH_THREADS) {
+            const int tk = item / dot.n_heads, h = item % dot.n_heads;
+            float z = 0.f;
+            for (int b0 = 0; b0 < nblk; b0 += 16) {               // 16 parts asked for at once, added in block order
+                float pt[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    pt[i] = b0 + i < nblk ? __hip_atomic_load(&dot.part[(((size_t)lr * nblk + b0 + i) * dot.n_heads + h) * n_tok + tk],
+                                                              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                          : 0.f;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) z += pt[i];
+            }
+            const float lb = log_sigmoid(z + dot.s[(size_t)lr * dot.n_heads + h]);
+            const size_t o = ((size_t)tk * dot.n_layers + layer_begin + lr) * dot.n_heads + h;
+            dot.log_beta_out[o] = lb;
+            if (dot.log_tail_out) dot.log_tail_out[o] = log_tail_of(lb, dot.horizon);
+        }
+        return;
+    }
     for (int idx = tid; idx < NT * 16 * ROWS; idx += GH_THREADS) {
         const int row = idx % ROWS, tk = (idx / ROWS) & 15, t = idx / (16 * ROWS);
         const int tok = tok0 + 16 * t + tk;
@@ -248,22 +337,6 @@ __device__ __forceinline__ uint16_t bf16_rne(float f) {
     uint32_t b = __float_as_uint(f);
     b += 0x7FFFu + ((b >> 16) & 1u);
     return (uint16_t)(b >> 16);
-}
-
-__device__ __forceinline__ float log_sigmoid(float z) {
-    return z >= 0.f ? -log1pf(expf(-z)) : z - log1pf(expf(z));
-}
-
-// log sum_{k<H} beta^k from log(beta); H <= 0: the limit -log(1 - beta)
-__device__ __forceinline__ float log_tail_of(float lb, int horizon) {
-    if (horizon <= 0) return -logf(-expm1f(lb));
-    const float beta = expf(lb);
-    float sum = 0.f, term = 1.f;
-    for (int k = 0; k < horizon; ++k) {
-        sum += term;
-        term *= beta;
-    }
-    return logf(sum);
 }
 
 __global__ __launch_bounds__(GR_THREADS) void k_gate_readout(GateView g, const float* __restrict__ u, int n_tok,
@@ -789,23 +862,42 @@ kvtrim_status launch_gate(kvtrim_ctx* ctx, const GateView& g, const float* prepa
         KVTRIM_HIP(ctx, hipGetLastError());
         return KVTRIM_OK;
     }
+    // up to 16 tokens with prepared weights: the readout rides in the first-layer kernel (its parts of the sums,
+    // heads * d_g / 16 numbers per token and layer, fit the scratch buffer's d_g when there are at most 16 heads)
+    if (prepared && n_tok <= 16 && n_heads <= 16) {
+        ProfScope prof(ctx, K_GATE_HIDDEN, st);
+        GateDot dot;
+        dot.v = pv;
+        dot.s = ps;
+        dot.part = scratch;
+        dot.done = ctx->ws.gate_done;
+        dot.log_beta_out = log_beta_out;
+        dot.log_tail_out = log_tail_out;
+        dot.n_heads = n_heads;
+        dot.n_layers = L;
+        dot.horizon = horizon;
+        hipLaunchKernelGGL((k_gate_hidden<1, 1, true, true>), dim3(g.d_g / GH_ROWS, nl, 1), dim3(GH_THREADS), 0, st, g, x, n_tok,
+                           layer_begin, ptiled, nullptr, dot);
+        KVTRIM_HIP(ctx, hipGetLastError());
+        return KVTRIM_OK;
+    }
     {
         ProfScope prof(ctx, K_GATE_HIDDEN, st);
         const dim3 grid1(g.d_g / GH_ROWS, nl, 1);
         const dim3 grid4(g.d_g / (4 * GH_ROWS), nl, 1);              // d_g is a multiple of 64
         if (n_tok <= 16 && prepared)
-            hipLaunchKernelGGL((k_gate_hidden<1, 1, true>), grid1, dim3(GH_THREADS), 0, st, g, x, n_tok, layer_begin, ptiled, scratch);
+            hipLaunchKernelGGL((k_gate_hidden<1, 1, true, false>), grid1, dim3(GH_THREADS), 0, st, g, x, n_tok, layer_begin, ptiled, scratch, GateDot{});
         else if (n_tok <= 32 && prepared)
-            hipLaunchKernelGGL((k_gate_hidden<2, 4, true>), grid4, dim3(GH_THREADS), 0, st, g, x, n_tok, layer_begin, ptiled, scratch);
+            hipLaunchKernelGGL((k_gate_hidden<2, 4, true, false>), grid4, dim3(GH_THREADS), 0, st, g, x, n_tok, layer_begin, ptiled, scratch, GateDot{});
         else if (n_tok <= 64 && prepared)
-            hipLaunchKernelGGL((k_gate_hidden<4, 4, true>), grid4, dim3(GH_THREADS), 0, st, g, x, n_tok, layer_begin, ptiled, scratch);
+            hipLaunchKernelGGL((k_gate_hidden<4, 4, true, false>), grid4, dim3(GH_THREADS), 0, st, g, x, n_tok, layer_begin, ptiled, scratch, GateDot{});
         else if (n_tok <= 16)
-            hipLaunchKernelGGL((k_gate_hidden<1, 1, false>), grid1, dim3(GH_THREADS), 0, st, g, x, n_tok, layer_begin, ptiled, scratch);
+            hipLaunchKernelGGL((k_gate_hidden<1, 1, false, false>), grid1, dim3(GH_THREADS), 0, st, g, x, n_tok, layer_begin, ptiled, scratch, GateDot{});
         else if (n_tok <= 32)
-            hipLaunchKernelGGL((k_gate_hidden<2, 4, false>), grid4, dim3(GH_THREADS), 0, st, g, x, n_tok, layer_begin, ptiled, scratch);
+            hipLaunchKernelGGL((k_gate_hidden<2, 4, false, false>), grid4, dim3(GH_THREADS), 0, st, g, x, n_tok, layer_begin, ptiled, scratch, GateDot{});
         else if (n_tok < 256)                                        // below that the tiled kernel cannot fill the chip
-            hipLaunchKernelGGL((k_gate_hidden<4, 4, false>), dim3(grid4.x, nl, (n_tok + 63) / 64), dim3(GH_THREADS), 0, st, g, x, n_tok,
-                               layer_begin, ptiled, scratch);
+            hipLaunchKernelGGL((k_gate_hidden<4, 4, false, false>), dim3(grid4.x, nl, (n_tok + 63) / 64), dim3(GH_THREADS), 0, st, g, x, n_tok,
+                               layer_begin, ptiled, scratch, GateDot{});
         else
             hipLaunchKernelGGL(k_gate_hidden_gemm, dim3((g.d_g + GG_BM - 1) / GG_BM, (n_tok + GG_BN - 1) / GG_BN, nl), dim3(256), 0,
                                st, g, x, n_tok, layer_begin, scratch);

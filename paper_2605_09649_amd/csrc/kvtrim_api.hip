@@ -33,7 +33,7 @@ static bool config_ok(const kvtrim_config* c) {
 }
 
 struct Layout {
-    size_t off[40];
+    size_t off[41];
     int32_t fl_cap;
     size_t total;
     int64_t max_sel_chunks, max_cmp_chunks, max_att_chunks, gat_slots;
@@ -107,6 +107,7 @@ static Layout layout_of(const kvtrim_config* c, bool select_only) {
     l.gat_slots = select_only ? 0 : c->max_entries / 4 + ((int64_t)nseg + 1) * CMP_CHUNK;
     l.off[38] = bump(cur, (size_t)l.gat_slots * sizeof(int32_t));              // gat_src
     l.off[39] = bump(cur, seg_tables * (size_t)(nseg + 1) * sizeof(int64_t));  // att_row_prefix
+    l.off[40] = bump(cur, (size_t)c->n_layers * sizeof(uint32_t));             // gate_done
     l.total = (cur + 255) & ~(size_t)255;
     return l;
 }
@@ -153,6 +154,7 @@ static void bind(const Layout& l, char* b, Workspace& w) {
     w.step_chunk_ev = (uint32_t*)(b + l.off[37]);
     w.gat_src = (int32_t*)(b + l.off[38]);
     w.att_row_prefix = (int64_t*)(b + l.off[39]);
+    w.gate_done = (uint32_t*)(b + l.off[40]);
     w.gat_slots = l.gat_slots;
     w.fl_cap = l.fl_cap;
     w.max_sel_chunks = l.max_sel_chunks;

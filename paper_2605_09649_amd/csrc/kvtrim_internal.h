@@ -198,6 +198,7 @@ struct Workspace {
     // destination chunk, written by the compaction scan
     int32_t* gat_src;            // [gat_slots]
     int64_t* att_row_prefix;     // [nseg+1] attention: rows (paged: slots) of the layer range's segments before each segment
+    uint32_t* gate_done;         // [n_layers] gate forward: blocks of a layer that have left their part of the readout (zero between calls)
     int64_t gat_slots;
     int64_t max_sel_chunks, max_cmp_chunks, max_att_chunks;
 };

@@ -152,7 +152,8 @@ def test_full_size_gate_prefill_chunk_on_sampled_tokens():
     (3, 2, 256, 64, 7, (1, 5, 20, 150)),          # per-token first layer + dot-product readout; hidden width not for the folded kernel
     (2, 3, 512, 128, 20, (16, 23, 24, 127, 300)),  # across the switch-over at 24 tokens: 32-token blocks read W1 from the prepared tiles
     (32, 2, 1280, 128, 8, (520,)),                 # 64-token blocks from the prepared tiles
-    (2, 8, 256, 512, 16, (64, 513, 1100)),         # the paper's hidden width, eight heads, 128-token blocks
+    (2, 8, 256, 512, 16, (1, 7, 16, 64, 513, 1100)),   # the paper's hidden width, eight heads: one kernel with the readout inside up to 16 tokens, 128-token blocks
+    (2, 17, 256, 64, 4, (3,)),                     # more than 16 heads: the readout's parts do not fit the scratch buffer, two kernels
     (2, 2, 256, 576, 8, (256,)),                   # hidden width above 512: LDS-tiled first layer + dot-product readout
 ])
 def test_prepared_gate_matches_the_oracle_and_is_reusable(L, H, d_model, d_g, d_p, n_toks):
@@ -175,6 +176,10 @@ def test_prepared_gate_matches_the_oracle_and_is_reusable(L, H, d_model, d_g, d_
             lt = torch.full((n_tok, L, H), float("nan"), dtype=torch.float32, device=DEV)
             kv.kvtrim_gate_forward_prepared(ctx, gate, prepared, x[lo:hi].contiguous().to(DEV), n_tok, lo, hi, 2, scratch, lb, lt)
             assert kv.kvtrim_poll_error(ctx) == 0
+            if n_tok <= 16:                                       # (the last block of a layer adds the parts of the readout: always in the same order)
+                lb2 = torch.full((n_tok, L, H), float("nan"), dtype=torch.float32, device=DEV)
+                kv.kvtrim_gate_forward_prepared(ctx, gate, prepared, x[lo:hi].contiguous().to(DEV), n_tok, lo, hi, 2, scratch, lb2, None)
+                assert torch.equal(lb[:, lo:hi], lb2[:, lo:hi])
             lb_h, lt_h = lb.cpu().numpy(), lt.cpu().numpy()
             assert np.isnan(lb_h[:, :lo, :]).all()                # layers outside the range stay untouched
             if pick is not None:
