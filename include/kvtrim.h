@@ -413,10 +413,12 @@ kvtrim_status kvtrim_paged_score_select(kvtrim_ctx *ctx, const kvtrim_paged_cach
                                         uint32_t *thr_key_out, int64_t evict_hint, void *hip_stream);
 
 /* A decode step on the paged layout in one call: leaves in the pages, score_out, keep_out, kept_out, thr_key_out, out
- * and lse exactly what
+ * and lse what
  *     kvtrim_paged_append(one token per segment) -> kvtrim_paged_score_select(now, budget, evict_hint)
  *     -> kvtrim_paged_evict(keep_out) -> kvtrim_paged_attn(q)
- * leave there (arguments as in those four calls; one row per segment in the new-token arrays).  With a small
+ * leave there (arguments as in those four calls; one row per segment in the new-token arrays) - bit for bit in
+ * everything but out / lse, which agree within the attention tolerance: a page that this step's eviction emptied is
+ * still listed when the attention's chunk table is built, so the fp32 sums may group differently.  With a small
  * evict_hint the mask kernel of the decode-step selection applies the eviction as it writes the mask (which saves
  * the pass of kvtrim_paged_evict over all pages), its scoring kernel also builds the attention's chunk table, and
  * the attention's merge kernel takes the emptied pages out of the block tables: five kernels per step.  Any other
